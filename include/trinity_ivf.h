@@ -1,0 +1,224 @@
+/*
+ * trinity_ivf.h -- C ABI of the MI355X vector-search pool worker.
+ *
+ * One GPU holds several IVF-Flat indexes resident in HBM (paper Sec. 3.2: the vectors and
+ * the index structure stay in device memory so that distance evaluation and expansion are
+ * pure device-memory operations) and serves retrieval requests of two priority classes
+ * (Sec. 3.3: a high-priority prefill queue and a lower-priority decode queue).  Requests are
+ * executed by CONTINUOUS BATCHING (Sec. 3.2): every call of search_step advances all running
+ * requests by one unit of work, packs the work of all of them into one cross-request task
+ * array evaluated by fixed-shape kernels, retires the requests that finished and admits
+ * waiting ones into the slots they vacated.  The paper describes this over a graph index
+ * (unit = one "extend"); here the index is IVF-Flat and the unit is the scan of up to `p`
+ * of a request's probed inverted lists.  Results do not depend on how requests are batched
+ * (Sec. 3.2, last paragraph).
+ *
+ * Conventions
+ *  - every function returns a tri_status (0 = ok, negative = error); nothing throws or aborts
+ *    across this boundary; tri_last_error() gives a thread-local text for the last failure.
+ *  - pointers marked [host] / [device] / [host|device] say where the memory must live.
+ *  - the library never takes ownership of caller memory except where stated (dev_ws, dev_mem).
+ *  - search_submit* may be called from several threads; search_step / search_poll /
+ *    search_sync from one driver thread at a time (calls are serialised by an internal lock).
+ *  - argument errors return TRI_EINVAL and change no state.
+ *  - there is no CPU fallback: without a usable HIP device every call that needs one fails
+ *    with TRI_EHIP.
+ */
+#ifndef TRINITY_IVF_H
+#define TRINITY_IVF_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct tri_pool tri_pool;   /* slot table, queues, workspaces; one per GPU          */
+typedef struct tri_index tri_index; /* one resident IVF-Flat index, attached to a pool      */
+typedef uint64_t tri_ticket;        /* names one submitted query until it is polled         */
+
+typedef enum {
+    TRI_OK = 0,
+    TRI_EINVAL = -1, /* bad argument                                                        */
+    TRI_ENOMEM = -2, /* workspace too small / table full in a way that waiting cannot fix    */
+    TRI_EAGAIN = -3, /* not yet (poll) / queue full, try again later (submit)               */
+    TRI_EHIP = -4,   /* a HIP call failed; see tri_last_error()                             */
+    TRI_ENOENT = -5  /* unknown, cancelled or already polled ticket                         */
+} tri_status;
+
+enum { TRI_L2 = 0, TRI_IP = 1 };          /* metric: squared L2 (smaller = better), inner product (larger = better) */
+enum { TRI_F32 = 0, TRI_F16 = 1 };        /* storage type of an index's vectors and of its queries                  */
+enum { TRI_CLASS_HIGH = 0, TRI_CLASS_LOW = 1 }; /* Sec. 3.3: prefill-side (latency critical) / decode-side requests */
+enum { TRI_FLAG_PROFILE = 1u,             /* bracket every kernel of a step with HIP events (tri_pool_kernel_times)  */
+       TRI_FLAG_KEEP_PROBES = 2u };       /* copy each query's probe list back so search_probes() can return it      */
+
+/* Limits of this implementation (checked, TRI_EINVAL beyond them). */
+#define TRI_KMAX_LIMIT 1024u      /* largest k a pool can be configured for           */
+#define TRI_NPROBE_LIMIT 1024u    /* largest nprobe a pool can be configured for      */
+#define TRI_MAX_ROW_BYTES 4096u   /* padded vector row: dim <= 2048 (fp16), 1024 (fp32) */
+
+typedef struct {
+    uint32_t slots;                /* S: running requests held at once (Sec. 3.3 "available slots")        */
+    uint32_t items_per_step;       /* W: capacity of the cross-request task array, in (query, list) items    */
+    uint32_t lists_per_query_step; /* p: lists a request may scan per step; 0 = all that remain             */
+    uint32_t kmax;                 /* largest k accepted                                                   */
+    uint32_t nprobe_max;           /* largest nprobe accepted                                              */
+    uint32_t max_indexes;          /* indexes that may be attached                                         */
+    uint32_t max_total_lists;      /* sum of nlist over all attached indexes                               */
+    uint32_t max_nlist;            /* largest nlist of one index                                           */
+    uint32_t max_dim;              /* largest dim of one index                                             */
+    uint32_t max_outstanding;      /* tickets alive at once (pending + running + finished, not yet polled)  */
+    uint32_t coarse_rows;          /* new queries ranked against centroids per launch (0 = default 1024)    */
+    uint32_t flags;                /* TRI_FLAG_*                                                           */
+    uint64_t score_capacity;       /* candidate scores one step may produce (elements, 4 B each); 0 = W*1024 */
+    void *hip_stream;              /* hipStream_t all work is enqueued on (NULL = the null stream)          */
+} tri_pool_cfg;
+
+/* Bytes of device workspace a pool with this configuration needs (256-byte aligned start). */
+int tri_pool_workspace_bytes(const tri_pool_cfg *cfg /*[host]*/, size_t *dev_bytes /*[host] out*/);
+
+/* Create a pool on the current HIP device.  dev_ws [device]: at least the size reported above,
+ * owned by the pool until tri_pool_destroy (the caller frees it afterwards).  Pinned host
+ * staging is allocated here (hipHostMalloc); no device memory is allocated by the pool. */
+int tri_pool_create(const tri_pool_cfg *cfg /*[host]*/, void *dev_ws /*[device]*/, size_t dev_ws_bytes,
+                    tri_pool **out /*[host] out*/);
+
+/* Destroy the pool.  Waits for enqueued work; every ticket becomes invalid.  Indexes attached
+ * to it must be destroyed first (TRI_EINVAL otherwise). */
+int tri_pool_destroy(tri_pool *pool);
+
+/* ---------------------------------------------------------------------------------------
+ * Index construction (not on the timed path).  IVF-Flat: nlist centroids, every base vector
+ * stored in the inverted list of its best centroid under build_metric (IVF is the index
+ * family named in the paper's introduction; its graph index is replaced by this).
+ * ------------------------------------------------------------------------------------- */
+typedef struct {
+    uint32_t dim;          /* vector length (elements); stored rows are zero-padded to a multiple of 128 B */
+    uint32_t nlist;        /* number of inverted lists                                             */
+    uint32_t dtype;        /* TRI_F32 / TRI_F16: type of base, queries and stored centroids         */
+    uint32_t build_metric; /* TRI_L2: Lloyd k-means, TRI_IP: spherical k-means (normalised means)   */
+    uint32_t train_iters;  /* Lloyd iterations run from the initial centroids (0 = use them as given) */
+    uint64_t seed;         /* seeds the choice of initial rows when no centroids are given          */
+} ivf_params;
+
+/* Device bytes the finished index occupies for n base vectors. */
+int ivf_build_bytes(const ivf_params *p /*[host]*/, uint64_t n, size_t *dev_bytes /*[host] out*/);
+
+/* Build an index and attach it to the pool.
+ *  base [host|device]: row-major n x dim, of p->dtype; copied and reordered list by list, the
+ *      caller may free it when the call returns.
+ *  centroids [host] or NULL: nlist x dim fp32 initial centroids.  NULL: nlist distinct base rows
+ *      chosen from p->seed.  Training uses all rows when n <= 256*nlist, otherwise a fixed
+ *      pseudo-random subset of 256*nlist rows; an empty cluster keeps its centroid.
+ *  dev_mem [device]: ivf_build_bytes() bytes, 256-byte aligned; owned by the index until
+ *      ivf_destroy.  Temporary build memory is allocated and freed inside the call.
+ * Synchronous.  Must not run while the pool has queries in flight (TRI_EINVAL). */
+int ivf_build(tri_pool *pool, const ivf_params *p /*[host]*/, const void *base /*[host|device]*/, uint64_t n,
+              const float *centroids /*[host] or NULL*/, void *dev_mem /*[device]*/, size_t dev_mem_bytes,
+              tri_index **out /*[host] out*/);
+
+/* Copy the searchable content of an index to host arrays: centroids [nlist x dim] -- exactly the
+ * stored values the coarse ranking uses, widened to fp32 --, list_off [nlist+1], list_ids [n]
+ * (base-row numbers, list after list, ascending inside a list).  Any pointer may be NULL. */
+int ivf_export(const tri_index *index, float *centroids /*[host]*/, uint64_t *list_off /*[host]*/,
+               int64_t *list_ids /*[host]*/);
+
+/* Shape of an index: n, dim, nlist, dtype, longest list.  Any pointer may be NULL. */
+int ivf_info(const tri_index *index, uint64_t *n, uint32_t *dim, uint32_t *nlist, uint32_t *dtype,
+             uint32_t *max_list_len);
+
+/* Detach and forget the index (its dev_mem returns to the caller).  TRI_EINVAL while the pool
+ * has queries in flight. */
+int ivf_destroy(tri_index *index);
+
+/* ---------------------------------------------------------------------------------------
+ * Search.  One query = one request of Sec. 3.2: it waits in its class's queue, is admitted
+ * into a free slot at a step boundary, contributes work items to successive steps and is
+ * retired -- its slot recycled -- in the step that scans its last probed list.
+ * ------------------------------------------------------------------------------------- */
+typedef struct {
+    const tri_index *index; /* target index (attached to the pool)                                 */
+    const void *vec;        /* [host] dim elements of the index's dtype; copied at submit            */
+    uint32_t k;             /* 1..kmax results wanted                                               */
+    uint32_t nprobe;        /* 1..min(nprobe_max, nlist) inverted lists to scan                     */
+    uint32_t metric;        /* TRI_L2 / TRI_IP: used for the coarse ranking AND the list scan       */
+    uint32_t klass;         /* TRI_CLASS_HIGH / TRI_CLASS_LOW                                       */
+    uint64_t deadline_ns;   /* carried, reported back; not yet used for ordering                    */
+    uint64_t user_tag;      /* carried, not interpreted                                             */
+} tri_query;
+
+/* Queue one query / n queries.  TRI_EAGAIN: max_outstanding tickets are alive (none queued by
+ * this call; for a batch, the first *n_done were queued). */
+int search_submit(tri_pool *pool, const tri_query *q /*[host]*/, tri_ticket *out /*[host] out*/);
+int search_submit_batch(tri_pool *pool, const tri_query *q /*[host] n*/, uint32_t n,
+                        tri_ticket *out /*[host] n*/, uint32_t *n_done /*[host] out or NULL*/);
+
+typedef struct {
+    uint64_t step;        /* sequence number of this step                                          */
+    uint32_t admitted;    /* queries moved from the queues into slots                              */
+    uint32_t retired;     /* queries whose last list is scanned by this step                       */
+    uint32_t running;     /* slots occupied while the step runs                                    */
+    uint32_t items;       /* real (query, list) work items packed                                  */
+    uint32_t capacity;    /* W: the difference to `items` is masked padding                        */
+    uint32_t pending_high, pending_low; /* still waiting after admission                           */
+    uint32_t finished;    /* tickets whose results became pollable during this call                 */
+} tri_step_stats;
+
+/* One step: admit (high class first, FIFO inside a class) -> coarse ranking of the admitted
+ * queries -> pack the work items of all running queries (items of queries admitted in this
+ * very call included; higher class first when W is short) -> list scan -> per-query top-k
+ * merge -> retire.  Only enqueues GPU work and returns; results of the retired queries become
+ * pollable when that work completes.  A call with nothing to do is a no-op. */
+int search_step(tri_pool *pool, tri_step_stats *stats /*[host] out or NULL*/);
+
+/* Result of a finished query, best first (L2 ascending, IP descending; equal scores by
+ * ascending id).  ids/dist [host]: room for the query's k entries.  *n_out = number of valid
+ * entries (fewer than k only if the probed lists hold fewer vectors); the tail is filled with
+ * id -1 and +inf (L2) / -inf (IP).  Ids are base-row numbers.  TRI_OK consumes the ticket;
+ * TRI_EAGAIN = not finished yet (does not block); TRI_ENOENT = no such ticket. */
+int search_poll(tri_pool *pool, tri_ticket t, uint32_t *n_out, int64_t *ids /*[host] k*/, float *dist /*[host] k*/);
+
+/* search_poll for n tickets in one call.  ids/dist [host]: n rows of `stride` entries, stride >= every
+ * polled ticket's k (a row is filled like search_poll fills its arrays).  status[i] receives what
+ * search_poll would have returned for ticket i.  Returns the number of tickets delivered (>= 0), or a
+ * negative tri_status for an argument error. */
+int search_poll_batch(tri_pool *pool, const tri_ticket *t /*[host] n*/, uint32_t n, uint32_t stride,
+                      uint32_t *n_out /*[host] n*/, int64_t *ids /*[host] n*stride*/, float *dist /*[host] n*stride*/,
+                      int *status /*[host] n*/);
+
+/* The probe list (centroid numbers, best first) of a finished, not yet polled query; needs
+ * TRI_FLAG_KEEP_PROBES.  lists [host]: room for the query's nprobe entries. */
+int search_probes(tri_pool *pool, tri_ticket t, uint32_t *lists /*[host]*/, uint32_t *n_out);
+
+/* Drop a query.  Queued: removed at once.  Running: runs to completion, result discarded.
+ * Finished: result discarded. */
+int search_cancel(tri_pool *pool, tri_ticket t);
+
+/* Block until all enqueued steps have completed and their results are pollable. */
+int search_sync(tri_pool *pool);
+
+/* Accumulated GPU time per kernel class since pool creation or the last reset (needs
+ * TRI_FLAG_PROFILE; measured with HIP events on the pool's stream around each launch group). */
+typedef struct {
+    uint64_t steps;          /* profiled steps accumulated                                        */
+    double admit_ms;         /* query rows into slots                                              */
+    double coarse_ms;        /* centroid contraction + top-nprobe selection                        */
+    double pack_ms;          /* work-item array and tile table                                     */
+    double scan_ms;          /* list scan                                                          */
+    double select_ms;        /* per-query top-k merge, result copy-out enqueue                     */
+    uint64_t scan_launches;  /* list-scan kernel launches                                          */
+    uint64_t scan_vector_bytes; /* bytes of inverted-list vectors those launches had to read: each
+                                   (list, query-group) tile counted once                          */
+    uint64_t scan_unique_bytes; /* same, each distinct list counted once per step                  */
+    uint64_t scan_items;     /* work items scanned                                                 */
+} tri_kernel_times;
+int tri_pool_kernel_times(tri_pool *pool, tri_kernel_times *out /*[host] out*/, int reset);
+
+const char *tri_last_error(void);
+const char *tri_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* TRINITY_IVF_H */

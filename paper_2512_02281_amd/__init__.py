@@ -1,0 +1,337 @@
+"""Thin Python binding of the MI355X vector-search pool library (argument marshalling only).
+
+Every function here has the name of the C entry point it forwards to (include/trinity_ivf.h);
+every step of the search path runs in the library's HIP kernels.  PyTorch appears only as the
+owner of device memory (workspaces, index storage) and of the stream.  There is no fallback: if
+the shared library has not been built, importing this package raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional, Sequence
+
+import numpy as np
+
+TRI_OK, TRI_EINVAL, TRI_ENOMEM, TRI_EAGAIN, TRI_EHIP, TRI_ENOENT = 0, -1, -2, -3, -4, -5
+TRI_L2, TRI_IP = 0, 1
+TRI_F32, TRI_F16 = 0, 1
+TRI_CLASS_HIGH, TRI_CLASS_LOW = 0, 1
+TRI_FLAG_PROFILE, TRI_FLAG_KEEP_PROBES = 1, 2
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libtrinity_ivf.so")
+
+
+class TriError(RuntimeError):
+    def __init__(self, status: int, where: str, text: str):
+        super().__init__(f"{where} -> status {status}: {text}")
+        self.status = status
+
+
+class tri_pool_cfg(ctypes.Structure):
+    _fields_ = [("slots", ctypes.c_uint32), ("items_per_step", ctypes.c_uint32),
+                ("lists_per_query_step", ctypes.c_uint32), ("kmax", ctypes.c_uint32),
+                ("nprobe_max", ctypes.c_uint32), ("max_indexes", ctypes.c_uint32),
+                ("max_total_lists", ctypes.c_uint32), ("max_nlist", ctypes.c_uint32),
+                ("max_dim", ctypes.c_uint32), ("max_outstanding", ctypes.c_uint32),
+                ("coarse_rows", ctypes.c_uint32), ("flags", ctypes.c_uint32),
+                ("score_capacity", ctypes.c_uint64), ("hip_stream", ctypes.c_void_p)]
+
+
+class ivf_params(ctypes.Structure):
+    _fields_ = [("dim", ctypes.c_uint32), ("nlist", ctypes.c_uint32), ("dtype", ctypes.c_uint32),
+                ("build_metric", ctypes.c_uint32), ("train_iters", ctypes.c_uint32),
+                ("seed", ctypes.c_uint64)]
+
+
+class tri_query(ctypes.Structure):
+    _fields_ = [("index", ctypes.c_void_p), ("vec", ctypes.c_void_p), ("k", ctypes.c_uint32),
+                ("nprobe", ctypes.c_uint32), ("metric", ctypes.c_uint32), ("klass", ctypes.c_uint32),
+                ("deadline_ns", ctypes.c_uint64), ("user_tag", ctypes.c_uint64)]
+
+
+# numpy view of the same struct, for building many queries without a Python loop
+QUERY_DTYPE = np.dtype([("index", np.uint64), ("vec", np.uint64), ("k", np.uint32), ("nprobe", np.uint32),
+                        ("metric", np.uint32), ("klass", np.uint32), ("deadline_ns", np.uint64),
+                        ("user_tag", np.uint64)], align=True)
+assert QUERY_DTYPE.itemsize == ctypes.sizeof(tri_query)
+
+
+class tri_step_stats(ctypes.Structure):
+    _fields_ = [("step", ctypes.c_uint64), ("admitted", ctypes.c_uint32), ("retired", ctypes.c_uint32),
+                ("running", ctypes.c_uint32), ("items", ctypes.c_uint32), ("capacity", ctypes.c_uint32),
+                ("pending_high", ctypes.c_uint32), ("pending_low", ctypes.c_uint32),
+                ("finished", ctypes.c_uint32)]
+
+
+class tri_kernel_times(ctypes.Structure):
+    _fields_ = [("steps", ctypes.c_uint64), ("admit_ms", ctypes.c_double), ("coarse_ms", ctypes.c_double),
+                ("pack_ms", ctypes.c_double), ("scan_ms", ctypes.c_double), ("select_ms", ctypes.c_double),
+                ("scan_launches", ctypes.c_uint64), ("scan_vector_bytes", ctypes.c_uint64),
+                ("scan_unique_bytes", ctypes.c_uint64), ("scan_items", ctypes.c_uint64)]
+
+
+EXPORTS = ["tri_pool_workspace_bytes", "tri_pool_create", "tri_pool_destroy", "ivf_build_bytes", "ivf_build",
+           "ivf_export", "ivf_info", "ivf_destroy", "search_submit", "search_submit_batch", "search_step",
+           "search_poll", "search_poll_batch", "search_probes", "search_cancel", "search_sync",
+           "tri_pool_kernel_times", "tri_last_error", "tri_version"]
+
+
+def _load():
+    if not os.path.exists(LIB_PATH):
+        raise ImportError(f"{LIB_PATH} is missing: build it first (python -c 'import __graft_entry__ as g; g.build()'); "
+                          "this package has no fallback path")
+    lib = ctypes.CDLL(LIB_PATH)
+    vp, u32, u64, sz = ctypes.c_void_p, ctypes.c_uint32, ctypes.c_uint64, ctypes.c_size_t
+    P = ctypes.POINTER
+    lib.tri_pool_workspace_bytes.argtypes = [P(tri_pool_cfg), P(sz)]
+    lib.tri_pool_create.argtypes = [P(tri_pool_cfg), vp, sz, P(vp)]
+    lib.tri_pool_destroy.argtypes = [vp]
+    lib.ivf_build_bytes.argtypes = [P(ivf_params), u64, P(sz)]
+    lib.ivf_build.argtypes = [vp, P(ivf_params), vp, u64, vp, vp, sz, P(vp)]
+    lib.ivf_export.argtypes = [vp, vp, vp, vp]
+    lib.ivf_info.argtypes = [vp, P(u64), P(u32), P(u32), P(u32), P(u32)]
+    lib.ivf_destroy.argtypes = [vp]
+    lib.search_submit.argtypes = [vp, P(tri_query), P(u64)]
+    lib.search_submit_batch.argtypes = [vp, vp, u32, vp, P(u32)]
+    lib.search_step.argtypes = [vp, P(tri_step_stats)]
+    lib.search_poll.argtypes = [vp, u64, P(u32), vp, vp]
+    lib.search_poll_batch.argtypes = [vp, vp, u32, u32, vp, vp, vp, vp]
+    lib.search_probes.argtypes = [vp, u64, vp, P(u32)]
+    lib.search_cancel.argtypes = [vp, u64]
+    lib.search_sync.argtypes = [vp]
+    lib.tri_pool_kernel_times.argtypes = [vp, P(tri_kernel_times), ctypes.c_int]
+    lib.tri_last_error.restype = ctypes.c_char_p
+    lib.tri_version.restype = ctypes.c_char_p
+    for name in EXPORTS:
+        if name not in ("tri_last_error", "tri_version"):
+            getattr(lib, name).restype = ctypes.c_int
+    return lib
+
+
+_lib = _load()
+
+
+def tri_last_error() -> str:
+    return _lib.tri_last_error().decode()
+
+
+def tri_version() -> str:
+    return _lib.tri_version().decode()
+
+
+def _check(rc: int, where: str, ok=(TRI_OK,)) -> int:
+    if rc not in ok:
+        raise TriError(rc, where, tri_last_error())
+    return rc
+
+
+def _np_ptr(a: Optional[np.ndarray]):
+    return None if a is None else a.ctypes.data_as(ctypes.c_void_p)
+
+
+# ------------------------------------------------------------------------------------------- pool
+def tri_pool_workspace_bytes(cfg: tri_pool_cfg) -> int:
+    out = ctypes.c_size_t(0)
+    _check(_lib.tri_pool_workspace_bytes(ctypes.byref(cfg), ctypes.byref(out)), "tri_pool_workspace_bytes")
+    return int(out.value)
+
+
+def tri_pool_create(cfg: tri_pool_cfg, dev_ws_ptr: int, dev_ws_bytes: int) -> int:
+    out = ctypes.c_void_p(None)
+    _check(_lib.tri_pool_create(ctypes.byref(cfg), ctypes.c_void_p(dev_ws_ptr), dev_ws_bytes, ctypes.byref(out)),
+           "tri_pool_create")
+    return out.value
+
+
+def tri_pool_destroy(pool: int) -> None:
+    _check(_lib.tri_pool_destroy(ctypes.c_void_p(pool)), "tri_pool_destroy")
+
+
+def tri_pool_kernel_times(pool: int, reset: bool = False) -> tri_kernel_times:
+    out = tri_kernel_times()
+    _check(_lib.tri_pool_kernel_times(ctypes.c_void_p(pool), ctypes.byref(out), int(reset)), "tri_pool_kernel_times")
+    return out
+
+
+# ------------------------------------------------------------------------------------------- index
+def ivf_build_bytes(params: ivf_params, n: int) -> int:
+    out = ctypes.c_size_t(0)
+    _check(_lib.ivf_build_bytes(ctypes.byref(params), n, ctypes.byref(out)), "ivf_build_bytes")
+    return int(out.value)
+
+
+def ivf_build(pool: int, params: ivf_params, base_ptr: int, n: int, centroids: Optional[np.ndarray],
+              dev_mem_ptr: int, dev_mem_bytes: int) -> int:
+    """base_ptr: host or device address of the row-major n x dim base (of params.dtype)."""
+    if centroids is not None:
+        centroids = np.ascontiguousarray(centroids, dtype=np.float32)
+        assert centroids.shape == (params.nlist, params.dim)
+    out = ctypes.c_void_p(None)
+    _check(_lib.ivf_build(ctypes.c_void_p(pool), ctypes.byref(params), ctypes.c_void_p(base_ptr), n,
+                          _np_ptr(centroids), ctypes.c_void_p(dev_mem_ptr), dev_mem_bytes, ctypes.byref(out)),
+           "ivf_build")
+    return out.value
+
+
+def ivf_info(index: int) -> dict:
+    n, dim, nlist, dtype, mx = ctypes.c_uint64(), ctypes.c_uint32(), ctypes.c_uint32(), ctypes.c_uint32(), ctypes.c_uint32()
+    _check(_lib.ivf_info(ctypes.c_void_p(index), ctypes.byref(n), ctypes.byref(dim), ctypes.byref(nlist),
+                         ctypes.byref(dtype), ctypes.byref(mx)), "ivf_info")
+    return dict(n=int(n.value), dim=int(dim.value), nlist=int(nlist.value), dtype=int(dtype.value),
+                max_list_len=int(mx.value))
+
+
+def ivf_export(index: int):
+    """(centroids fp32 [nlist, dim], list_off uint64 [nlist+1], list_ids int64 [n])."""
+    info = ivf_info(index)
+    cent = np.empty((info["nlist"], info["dim"]), dtype=np.float32)
+    off = np.empty(info["nlist"] + 1, dtype=np.uint64)
+    ids = np.empty(info["n"], dtype=np.int64)
+    _check(_lib.ivf_export(ctypes.c_void_p(index), _np_ptr(cent), _np_ptr(off), _np_ptr(ids)), "ivf_export")
+    return cent, off, ids
+
+
+def ivf_destroy(index: int) -> None:
+    _check(_lib.ivf_destroy(ctypes.c_void_p(index)), "ivf_destroy")
+
+
+# ------------------------------------------------------------------------------------------- search
+def search_submit(pool: int, index: int, vec: np.ndarray, k: int, nprobe: int, metric: int,
+                  klass: int = TRI_CLASS_LOW, deadline_ns: int = 0, user_tag: int = 0) -> int:
+    vec = np.ascontiguousarray(vec)
+    q = tri_query(index, vec.ctypes.data, k, nprobe, metric, klass, deadline_ns, user_tag)
+    out = ctypes.c_uint64(0)
+    _check(_lib.search_submit(ctypes.c_void_p(pool), ctypes.byref(q), ctypes.byref(out)), "search_submit")
+    return int(out.value)
+
+
+def make_queries(index, vecs: np.ndarray, k, nprobe, metric, klass=TRI_CLASS_LOW) -> np.ndarray:
+    """An array of tri_query records over the rows of `vecs` (which must stay alive until submitted).
+    index / k / nprobe / metric / klass: scalars or per-row arrays."""
+    assert vecs.flags["C_CONTIGUOUS"] and vecs.ndim == 2
+    n = vecs.shape[0]
+    q = np.zeros(n, dtype=QUERY_DTYPE)
+    q["index"] = index
+    q["vec"] = vecs.ctypes.data + np.arange(n, dtype=np.uint64) * np.uint64(vecs.strides[0])
+    q["k"], q["nprobe"], q["metric"], q["klass"] = k, nprobe, metric, klass
+    return q
+
+
+def search_submit_batch(pool: int, queries: np.ndarray):
+    """queries: array of QUERY_DTYPE.  Returns (tickets uint64 [n_done], status).  status TRI_EAGAIN
+    means only the first n_done were queued."""
+    assert queries.dtype == QUERY_DTYPE and queries.flags["C_CONTIGUOUS"]
+    n = queries.shape[0]
+    tickets = np.zeros(n, dtype=np.uint64)
+    done = ctypes.c_uint32(0)
+    rc = _lib.search_submit_batch(ctypes.c_void_p(pool), _np_ptr(queries), n, _np_ptr(tickets), ctypes.byref(done))
+    _check(rc, "search_submit_batch", ok=(TRI_OK, TRI_EAGAIN))
+    return tickets[:done.value], rc
+
+
+def search_step(pool: int, stats: Optional[tri_step_stats] = None) -> tri_step_stats:
+    st = stats if stats is not None else tri_step_stats()
+    _check(_lib.search_step(ctypes.c_void_p(pool), ctypes.byref(st)), "search_step")
+    return st
+
+
+def search_poll(pool: int, ticket: int, k: int):
+    """None while the query is not finished, else (ids int64 [k], dist fp32 [k], n_out)."""
+    ids = np.empty(k, dtype=np.int64)
+    dist = np.empty(k, dtype=np.float32)
+    n = ctypes.c_uint32(0)
+    rc = _lib.search_poll(ctypes.c_void_p(pool), ticket, ctypes.byref(n), _np_ptr(ids), _np_ptr(dist))
+    if rc == TRI_EAGAIN:
+        return None
+    _check(rc, "search_poll")
+    return ids, dist, int(n.value)
+
+
+def search_poll_batch(pool: int, tickets: np.ndarray, stride: int):
+    """(ids int64 [n, stride], dist fp32 [n, stride], n_out uint32 [n], status int32 [n])."""
+    tickets = np.ascontiguousarray(tickets, dtype=np.uint64)
+    n = tickets.shape[0]
+    ids = np.empty((n, stride), dtype=np.int64)
+    dist = np.empty((n, stride), dtype=np.float32)
+    n_out = np.zeros(n, dtype=np.uint32)
+    status = np.zeros(n, dtype=np.int32)
+    rc = _lib.search_poll_batch(ctypes.c_void_p(pool), _np_ptr(tickets), n, stride, _np_ptr(n_out), _np_ptr(ids),
+                                _np_ptr(dist), _np_ptr(status))
+    if rc < 0:
+        _check(rc, "search_poll_batch")
+    return ids, dist, n_out, status
+
+
+def search_probes(pool: int, ticket: int, nprobe: int) -> Optional[np.ndarray]:
+    lists = np.empty(nprobe, dtype=np.uint32)
+    n = ctypes.c_uint32(0)
+    rc = _lib.search_probes(ctypes.c_void_p(pool), ticket, _np_ptr(lists), ctypes.byref(n))
+    if rc == TRI_EAGAIN:
+        return None
+    _check(rc, "search_probes")
+    return lists[:n.value]
+
+
+def search_cancel(pool: int, ticket: int) -> None:
+    _check(_lib.search_cancel(ctypes.c_void_p(pool), ticket), "search_cancel")
+
+
+def search_sync(pool: int) -> None:
+    _check(_lib.search_sync(ctypes.c_void_p(pool)), "search_sync")
+
+
+# ------------------------------------------------------------------------------------------- holders
+class Pool:
+    """Owns the torch tensors that back a pool's device workspace and its indexes' storage."""
+
+    def __init__(self, **cfg_fields):
+        import torch
+        if not torch.cuda.is_available():
+            raise RuntimeError("no GPU: the search path has no CPU fallback")
+        self.cfg = tri_pool_cfg(**cfg_fields)
+        self.cfg.hip_stream = torch.cuda.current_stream().cuda_stream
+        nbytes = tri_pool_workspace_bytes(self.cfg)
+        self._ws = torch.empty(nbytes + 256, dtype=torch.uint8, device="cuda")
+        ptr = (self._ws.data_ptr() + 255) // 256 * 256
+        self.handle = tri_pool_create(self.cfg, ptr, nbytes)
+        self._index_mem = {}
+
+    def build_index(self, base, dim: int, nlist: int, dtype: int, build_metric: int, train_iters: int,
+                    centroids: Optional[np.ndarray] = None, seed: int = 0) -> int:
+        """base: torch tensor (cpu or cuda) or numpy array, row-major [n, dim] of the index dtype."""
+        import torch
+        params = ivf_params(dim, nlist, dtype, build_metric, train_iters, seed)
+        n = int(base.shape[0])
+        nbytes = ivf_build_bytes(params, n)
+        mem = torch.empty(nbytes + 256, dtype=torch.uint8, device="cuda")
+        ptr = (mem.data_ptr() + 255) // 256 * 256
+        if isinstance(base, np.ndarray):
+            base = np.ascontiguousarray(base)
+            base_ptr = base.ctypes.data
+        else:
+            base = base.contiguous()
+            base_ptr = base.data_ptr()
+        torch.cuda.current_stream().synchronize()
+        index = ivf_build(self.handle, params, base_ptr, n, centroids, ptr, nbytes)
+        self._index_mem[index] = mem
+        return index
+
+    def destroy_index(self, index: int) -> None:
+        ivf_destroy(index)
+        self._index_mem.pop(index, None)
+
+    def close(self) -> None:
+        if self.handle:
+            for index in list(self._index_mem):
+                self.destroy_index(index)
+            tri_pool_destroy(self.handle)
+            self.handle = None
+            self._ws = None
+
+    def __enter__(self):
+        return self
+
+    def __exit__(self, *exc):
+        self.close()

@@ -1,0 +1,234 @@
+// Admission and packing of one step (paper Sec. 3.2: every running request emits its next units of
+// work into one global, cross-request task array; the array has a fixed capacity and unused
+// entries are masked).  The work items (slot, list) of all running slots are grouped by inverted
+// list, so that the queries probing the same list share one read of it, and cut into scan tiles of
+// up to TRI_QT queries.
+#include "tri_common.h"
+
+// ---------------------------------------------------------------------------------------- fill
+__global__ void fill_u32_kernel(uint32_t *p, uint32_t v, size_t n)
+{
+    size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) p[i] = v;
+}
+
+hipError_t tri_launch_fill_u32(hipStream_t s, uint32_t *p, uint32_t v, size_t n)
+{
+    if (n == 0) return hipSuccess;
+    hipLaunchKernelGGL(fill_u32_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, p, v, n);
+    return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------------------- admit
+// One workgroup per admitted query: copy its padded row into the slot, compute |q|^2 in fp32
+// (fixed order: thread-strided partial sums, then a tree), write the slot's static description.
+__global__ __launch_bounds__(256) void admit_kernel(const TriNewDesc *__restrict__ desc,
+                                                    const uint8_t *__restrict__ rows,
+                                                    const TriIndexDev *__restrict__ indexes,
+                                                    uint8_t *__restrict__ slot_query, uint32_t slot_row_bytes,
+                                                    TriSlotMeta *__restrict__ slot_meta,
+                                                    float *__restrict__ slot_qnorm, uint32_t *__restrict__ topk_count)
+{
+    __shared__ float red[256];
+    const TriNewDesc d = desc[blockIdx.x];
+    const TriIndexDev &ix = indexes[d.index];
+    const uint8_t *src = rows + d.row_off;
+    uint8_t *dst = slot_query + (size_t)d.slot * slot_row_bytes;
+    const uint32_t n16 = ix.row_bytes / 16;
+    float part = 0.f;
+    for (uint32_t c = threadIdx.x; c < n16; c += 256) {
+        const uint4 v = *(const uint4 *)(src + c * 16);
+        *(uint4 *)(dst + c * 16) = v;
+        if (ix.dtype == 1u) {
+            const _Float16 *h = (const _Float16 *)&v;
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                const float f = (float)h[i];
+                part += f * f;
+            }
+        } else {
+            const float *f = (const float *)&v;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) part += f[i] * f[i];
+        }
+    }
+    red[threadIdx.x] = part;
+    __syncthreads();
+    for (uint32_t s = 128; s > 0; s >>= 1) {
+        if (threadIdx.x < s) red[threadIdx.x] += red[threadIdx.x + s];
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) {
+        slot_meta[d.slot] = TriSlotMeta{d.index, d.metric, d.k, d.nprobe};
+        slot_qnorm[d.slot] = red[0];
+        topk_count[d.slot] = 0;
+    }
+}
+
+hipError_t tri_launch_admit(const TriLaunchCtx &c, const TriDevWs &ws, const TriNewDesc *desc_dev,
+                            const uint8_t *rows_dev, uint32_t n_new)
+{
+    if (n_new == 0) return hipSuccess;
+    hipLaunchKernelGGL(admit_kernel, dim3(n_new), dim3(256), 0, c.stream, desc_dev, rows_dev, ws.indexes,
+                       ws.slot_query, c.slot_row_bytes, ws.slot_meta, ws.slot_qnorm, ws.topk_count);
+    return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------------------- pack
+// (1) emit: one thread per work item.  Item i of plan entry e (found by binary search over the
+//     entries' item_base) is list probe[slot][cursor + j]; its rank inside the list's group is
+//     taken from an atomic counter.  The rank decides only which tile row a query occupies; every
+//     score is computed independently of its neighbours, so results do not depend on it.
+__global__ void pack_emit_kernel(const TriPlanEntry *__restrict__ plan, uint32_t n_plan, uint32_t n_items,
+                                 const TriSlotMeta *__restrict__ slot_meta, const TriIndexDev *__restrict__ indexes,
+                                 const uint32_t *__restrict__ probe, uint32_t nprobe_max,
+                                 uint32_t *__restrict__ item_glist, uint32_t *__restrict__ item_slot,
+                                 uint32_t *__restrict__ item_rank, uint32_t *__restrict__ hist)
+{
+    const uint32_t i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= n_items) return;
+    uint32_t lo = 0, hi = n_plan;          // last entry with item_base <= i
+    while (hi - lo > 1) {
+        const uint32_t mid = (lo + hi) >> 1;
+        if (plan[mid].item_base <= i) lo = mid; else hi = mid;
+    }
+    const TriPlanEntry e = plan[lo];
+    const uint32_t j = i - e.item_base;
+    const uint32_t list = probe[(size_t)e.slot * nprobe_max + e.cursor + j];
+    const uint32_t g = indexes[slot_meta[e.slot].index].list_base + list;
+    item_glist[i] = g;
+    item_slot[i] = e.slot;
+    item_rank[i] = atomicAdd(&hist[g], 1u);
+}
+
+// (2) scan: one workgroup.  Exclusive prefix sums over the pool-wide list table of: items per list
+//     (-> list_start), tiles per list (-> tile_base), padded scores per list (-> score_base).
+//     Also the step totals and the reset of the scan kernel's work-queue head.
+__global__ __launch_bounds__(1024) void pack_scan_kernel(const uint32_t *__restrict__ hist, uint32_t total_lists,
+                                                         const uint32_t *__restrict__ glist_len,
+                                                         const uint32_t *__restrict__ glist_index,
+                                                         const TriIndexDev *__restrict__ indexes,
+                                                         uint32_t *__restrict__ list_start,
+                                                         uint32_t *__restrict__ tile_base,
+                                                         uint64_t *__restrict__ score_base,
+                                                         TriStepDev *__restrict__ step_dev,
+                                                         uint32_t *__restrict__ tile_counter)
+{
+    __shared__ uint32_t s_items[1024], s_tiles[1024], s_lists[1024];
+    __shared__ uint64_t s_scores[1024], s_tbytes[1024], s_ubytes[1024];
+    const uint32_t t = threadIdx.x;
+    const uint32_t per = (total_lists + 1023) / 1024;
+    const uint32_t g0 = t * per, g1 = min(g0 + per, total_lists);
+    uint32_t items = 0, tiles = 0, lists = 0;
+    uint64_t sc = 0, tb = 0, ub = 0;
+    for (uint32_t g = g0; g < g1; ++g) {
+        const uint32_t c = hist[g];
+        if (c) {
+            const uint32_t len = glist_len[g];
+            const uint32_t nt = (c + TRI_QT - 1) / TRI_QT;
+            const uint64_t bytes = (uint64_t)len * indexes[glist_index[g]].row_bytes;
+            items += c;
+            tiles += nt;
+            lists += 1;
+            sc += (uint64_t)c * ((len + TRI_VB - 1) / TRI_VB * TRI_VB);
+            tb += bytes * nt;
+            ub += bytes;
+        }
+    }
+    s_items[t] = items; s_tiles[t] = tiles; s_lists[t] = lists;
+    s_scores[t] = sc; s_tbytes[t] = tb; s_ubytes[t] = ub;
+    __syncthreads();
+    // Hillis-Steele inclusive scan over the 1024 thread totals
+    for (uint32_t d = 1; d < 1024; d <<= 1) {
+        uint32_t a = 0, b = 0, l = 0;
+        uint64_t x = 0, y = 0, z = 0;
+        if (t >= d) {
+            a = s_items[t - d]; b = s_tiles[t - d]; l = s_lists[t - d];
+            x = s_scores[t - d]; y = s_tbytes[t - d]; z = s_ubytes[t - d];
+        }
+        __syncthreads();
+        s_items[t] += a; s_tiles[t] += b; s_lists[t] += l;
+        s_scores[t] += x; s_tbytes[t] += y; s_ubytes[t] += z;
+        __syncthreads();
+    }
+    uint32_t it = s_items[t] - items, ti = s_tiles[t] - tiles;
+    uint64_t so = s_scores[t] - sc;
+    for (uint32_t g = g0; g < g1; ++g) {
+        const uint32_t c = hist[g];
+        list_start[g] = it;
+        tile_base[g] = ti;
+        score_base[g] = so;
+        if (c) {
+            const uint32_t len = glist_len[g];
+            it += c;
+            ti += (c + TRI_QT - 1) / TRI_QT;
+            so += (uint64_t)c * ((len + TRI_VB - 1) / TRI_VB * TRI_VB);
+        }
+    }
+    if (t == 1023) {
+        step_dev->n_tiles = s_tiles[t];
+        step_dev->n_lists_touched = s_lists[t];
+        step_dev->total_scores = s_scores[t];
+        step_dev->tile_vec_bytes = s_tbytes[t];
+        step_dev->unique_vec_bytes = s_ubytes[t];
+        *tile_counter = 0;
+    }
+}
+
+// (3) scatter: one thread per item -> list-sorted slot array and the item's score segment.
+__global__ void pack_scatter_kernel(uint32_t n_items, const uint32_t *__restrict__ item_glist,
+                                    const uint32_t *__restrict__ item_slot, const uint32_t *__restrict__ item_rank,
+                                    const uint32_t *__restrict__ list_start, const uint64_t *__restrict__ score_base,
+                                    const uint32_t *__restrict__ glist_len, uint32_t *__restrict__ sorted_slot,
+                                    uint64_t *__restrict__ item_score_off)
+{
+    const uint32_t i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= n_items) return;
+    const uint32_t g = item_glist[i], r = item_rank[i];
+    const uint32_t npad = (glist_len[g] + TRI_VB - 1) / TRI_VB * TRI_VB;
+    sorted_slot[list_start[g] + r] = item_slot[i];
+    item_score_off[i] = score_base[g] + (uint64_t)r * npad;
+}
+
+// (4) tiles: one thread per list of the pool-wide table.
+__global__ void pack_tiles_kernel(uint32_t total_lists, const uint32_t *__restrict__ hist,
+                                  const uint32_t *__restrict__ list_start, const uint32_t *__restrict__ tile_base,
+                                  const uint64_t *__restrict__ score_base, const uint32_t *__restrict__ glist_len,
+                                  TriTile *__restrict__ tiles)
+{
+    const uint32_t g = blockIdx.x * blockDim.x + threadIdx.x;
+    if (g >= total_lists) return;
+    const uint32_t c = hist[g];
+    if (!c) return;
+    const uint32_t npad = (glist_len[g] + TRI_VB - 1) / TRI_VB * TRI_VB;
+    const uint32_t nt = (c + TRI_QT - 1) / TRI_QT;
+    for (uint32_t q = 0; q < nt; ++q) {
+        TriTile tl;
+        tl.glist = g;
+        tl.item_pos = list_start[g] + q * TRI_QT;
+        tl.nq = min((uint32_t)TRI_QT, c - q * TRI_QT);
+        tl.pad_ = 0;
+        tl.score_off = score_base[g] + (uint64_t)q * TRI_QT * npad;
+        tiles[tile_base[g] + q] = tl;
+    }
+}
+
+hipError_t tri_launch_pack(const TriLaunchCtx &c, const TriDevWs &ws, const TriPlanEntry *plan_dev, uint32_t n_plan,
+                           uint32_t n_items, uint32_t total_lists)
+{
+    if (n_items == 0 || total_lists == 0) return hipSuccess;
+    hipError_t e = tri_launch_fill_u32(c.stream, ws.hist, 0u, total_lists);
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL(pack_emit_kernel, dim3((n_items + 255) / 256), dim3(256), 0, c.stream, plan_dev, n_plan,
+                       n_items, ws.slot_meta, ws.indexes, ws.probe, c.nprobe_max, ws.item_glist, ws.item_slot,
+                       ws.item_rank, ws.hist);
+    hipLaunchKernelGGL(pack_scan_kernel, dim3(1), dim3(1024), 0, c.stream, ws.hist, total_lists, ws.glist_len,
+                       ws.glist_index, ws.indexes, ws.list_start, ws.tile_base, ws.score_base, ws.step_dev,
+                       ws.tile_counter);
+    hipLaunchKernelGGL(pack_scatter_kernel, dim3((n_items + 255) / 256), dim3(256), 0, c.stream, n_items,
+                       ws.item_glist, ws.item_slot, ws.item_rank, ws.list_start, ws.score_base, ws.glist_len,
+                       ws.sorted_slot, ws.item_score_off);
+    hipLaunchKernelGGL(pack_tiles_kernel, dim3((total_lists + 255) / 256), dim3(256), 0, c.stream, total_lists,
+                       ws.hist, ws.list_start, ws.tile_base, ws.score_base, ws.glist_len, ws.tiles);
+    return hipGetLastError();
+}

@@ -1,0 +1,289 @@
+// Per-query top-k: a workgroup-level radix select over fp32 scores followed by a bitonic sort of
+// the k survivors (the paper's Sec. 3.2 step "scatter (id, dist) back to the owning request and
+// merge into its topM"; here the request's candidates of one step are the score segments of its
+// work items plus its running top-k).
+//
+// Order: ascending 64-bit composite (key << 32 | id), key = order-preserving image of the fp32
+// score (bit-flipped for inner product, so "smaller key" always means "better").  Equal scores are
+// therefore ordered by ascending id, which makes the result independent of how the candidates
+// were batched.
+//
+// Selection: three histogram passes (11 + 11 + 10 bits) find the key T of the k-th best element;
+// if more elements equal T than are still needed, three more passes over the ids of those
+// elements find the largest id to keep; one collect pass gathers exactly k pairs.
+#include "tri_common.h"
+
+#define SEL_BINS 2048
+
+__device__ __forceinline__ uint32_t sel_key(float f, uint32_t desc)
+{
+    uint32_t u = __float_as_uint(f);
+    if (u == 0x80000000u) u = 0;                       // -0 and +0 are the same score
+    u ^= (u >> 31) ? 0xFFFFFFFFu : 0x80000000u;        // ascending float order -> ascending unsigned
+    return desc ? ~u : u;
+}
+
+__device__ __forceinline__ float sel_unkey(uint32_t key, uint32_t desc)
+{
+    uint32_t u = desc ? ~key : key;
+    u ^= (u >> 31) ? 0x80000000u : 0xFFFFFFFFu;
+    return __uint_as_float(u);
+}
+
+// A candidate source: segments of (scores, ids).  ids == nullptr means id = id_base + position.
+struct SelSeg {
+    const float *scores;
+    const uint32_t *ids;
+    uint32_t len;
+    uint32_t id_base;
+};
+
+struct SelShared {
+    uint32_t hist[SEL_BINS];
+    uint64_t out[TRI_KMAX_POW2];
+    uint32_t wave_tot[8];
+    uint32_t digit, need, count, cnt;
+};
+
+// Inclusive scan of one value per thread across the workgroup (TRI_SEL_THREADS threads).
+__device__ __forceinline__ uint32_t sel_block_scan_incl(uint32_t v, uint32_t *wave_tot)
+{
+    const uint32_t lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    uint32_t x = v;
+#pragma unroll
+    for (int d = 1; d < 64; d <<= 1) {
+        uint32_t y = __shfl_up(x, d, 64);
+        if (lane >= (uint32_t)d) x += y;
+    }
+    if (lane == 63) wave_tot[wave] = x;
+    __syncthreads();
+    uint32_t add = 0;
+    for (uint32_t w = 0; w < wave; ++w) add += wave_tot[w];
+    __syncthreads();
+    return x + add;
+}
+
+// After a histogram pass: find the smallest digit D with cumulative count >= need.
+// Writes sh.digit = D, sh.need = need - (count of digits < D), sh.count = hist[D].
+__device__ __forceinline__ void sel_find_digit(SelShared &sh, uint32_t nbins, uint32_t need)
+{
+    const uint32_t per = nbins / TRI_SEL_THREADS;   // 8 or 4
+    const uint32_t b0 = threadIdx.x * per;
+    uint32_t mine = 0;
+    for (uint32_t i = 0; i < per; ++i) mine += sh.hist[b0 + i];
+    const uint32_t incl = sel_block_scan_incl(mine, sh.wave_tot);
+    const uint32_t excl = incl - mine;
+    if (excl < need && need <= incl) {
+        uint32_t run = excl;
+        for (uint32_t i = 0; i < per; ++i) {
+            const uint32_t h = sh.hist[b0 + i];
+            if (run + h >= need) {
+                sh.digit = b0 + i;
+                sh.need = need - run;
+                sh.count = h;
+                break;
+            }
+            run += h;
+        }
+    }
+    __syncthreads();
+}
+
+// Enumerate every candidate: f(key, seg, pos).  Wavefronts take segments round-robin.
+template <class SegFn, class Fn>
+__device__ __forceinline__ void sel_for_each(uint32_t nseg, SegFn seg_of, uint32_t desc, Fn f)
+{
+    const uint32_t lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    for (uint32_t s = wave; s < nseg; s += TRI_SEL_THREADS / 64) {
+        const SelSeg sg = seg_of(s);
+        for (uint32_t i = lane; i < sg.len; i += 64) f(sel_key(sg.scores[i], desc), sg, i);
+    }
+}
+
+// Select the k best of `total` candidates into sh.out[0..n) sorted ascending by (key, id).
+// Returns n = min(k, total).  All threads of the workgroup must call it.
+template <class SegFn>
+__device__ uint32_t sel_block_topk(SelShared &sh, uint32_t nseg, SegFn seg_of, uint32_t total, uint32_t k,
+                                   uint32_t desc)
+{
+    const uint32_t tid = threadIdx.x;
+    uint32_t T = 0xFFFFFFFFu, Tid = 0xFFFFFFFFu;
+    const uint32_t n = total < k ? total : k;
+    if (total > k) {
+        // ---- key of the k-th best element
+        uint32_t need = k, prefix = 0;
+        const uint32_t shifts[3] = {21, 10, 0}, widths[3] = {11, 11, 10};
+        uint32_t count_eq = 0;
+        for (int pass = 0; pass < 3; ++pass) {
+            const uint32_t shift = shifts[pass], width = widths[pass], nb = 1u << width;
+            for (uint32_t i = tid; i < SEL_BINS; i += TRI_SEL_THREADS) sh.hist[i] = 0;
+            __syncthreads();
+            const uint32_t hi_shift = shift + width;
+            sel_for_each(nseg, seg_of, desc, [&](uint32_t key, const SelSeg &, uint32_t) {
+                if (pass == 0 || (key >> hi_shift) == prefix) atomicAdd(&sh.hist[(key >> shift) & (nb - 1)], 1u);
+            });
+            __syncthreads();
+            sel_find_digit(sh, nb, need);
+            prefix = (prefix << width) | sh.digit;
+            need = sh.need;
+            count_eq = sh.count;
+            __syncthreads();
+        }
+        T = prefix;
+        // ---- ties at T: keep the `need` smallest ids among the count_eq elements equal to T
+        if (need < count_eq) {
+            uint32_t idprefix = 0, need_id = need;
+            for (int pass = 0; pass < 3; ++pass) {
+                const uint32_t shift = shifts[pass], width = widths[pass], nb = 1u << width;
+                for (uint32_t i = tid; i < SEL_BINS; i += TRI_SEL_THREADS) sh.hist[i] = 0;
+                __syncthreads();
+                const uint32_t hi_shift = shift + width;
+                sel_for_each(nseg, seg_of, desc, [&](uint32_t key, const SelSeg &sg, uint32_t i) {
+                    if (key != T) return;
+                    const uint32_t id = sg.ids ? sg.ids[i] : sg.id_base + i;
+                    if (pass == 0 || (id >> hi_shift) == idprefix) atomicAdd(&sh.hist[(id >> shift) & (nb - 1)], 1u);
+                });
+                __syncthreads();
+                sel_find_digit(sh, nb, need_id);
+                idprefix = (idprefix << width) | sh.digit;
+                need_id = sh.need;
+                __syncthreads();
+            }
+            Tid = idprefix;
+        }
+    }
+    // ---- collect
+    if (tid == 0) sh.cnt = 0;
+    __syncthreads();
+    sel_for_each(nseg, seg_of, desc, [&](uint32_t key, const SelSeg &sg, uint32_t i) {
+        if (key > T) return;
+        const uint32_t id = sg.ids ? sg.ids[i] : sg.id_base + i;
+        if (key == T && id > Tid) return;
+        const uint32_t pos = atomicAdd(&sh.cnt, 1u);
+        if (pos < TRI_KMAX_POW2) sh.out[pos] = ((uint64_t)key << 32) | id;
+    });
+    __syncthreads();
+    // ---- sort the survivors (bitonic, padded with the largest composite)
+    uint32_t np2 = 1;
+    while (np2 < n) np2 <<= 1;
+    for (uint32_t i = n + tid; i < np2; i += TRI_SEL_THREADS) sh.out[i] = ~0ull;
+    __syncthreads();
+    for (uint32_t size = 2; size <= np2; size <<= 1) {
+        for (uint32_t stride = size >> 1; stride > 0; stride >>= 1) {
+            for (uint32_t i = tid; i < np2 / 2; i += TRI_SEL_THREADS) {
+                const uint32_t lo = 2 * i - (i & (stride - 1));   // index with the `stride` bit clear
+                const uint32_t hi = lo + stride;
+                const bool up = (lo & size) == 0;
+                const uint64_t a = sh.out[lo], b = sh.out[hi];
+                if ((a > b) == up) {
+                    sh.out[lo] = b;
+                    sh.out[hi] = a;
+                }
+            }
+            __syncthreads();
+        }
+    }
+    return n;
+}
+
+// ------------------------------------------------------------------------------------------------
+// Coarse selection: probe list of each newly admitted query = the nprobe best centroids, best
+// first, ties -> smaller centroid number.
+__global__ __launch_bounds__(TRI_SEL_THREADS) void coarse_select_kernel(
+    const float *__restrict__ scores, uint32_t ldc, uint32_t nlist, const TriNewDesc *__restrict__ desc,
+    uint32_t first_new, uint32_t *__restrict__ probe, uint32_t nprobe_max)
+{
+    __shared__ SelShared sh;
+    const TriNewDesc d = desc[first_new + blockIdx.x];
+    const float *row = scores + (size_t)blockIdx.x * ldc;
+    auto seg_of = [&](uint32_t) { return SelSeg{row, nullptr, nlist, 0u}; };
+    const uint32_t n = sel_block_topk(sh, 1u, seg_of, nlist, d.nprobe, d.metric);
+    uint32_t *dst = probe + (size_t)d.slot * nprobe_max;
+    for (uint32_t i = threadIdx.x; i < n; i += TRI_SEL_THREADS) dst[i] = (uint32_t)(sh.out[i] & 0xFFFFFFFFu);
+}
+
+hipError_t tri_launch_coarse_select(const TriLaunchCtx &c, const TriDevWs &ws, const TriNewDesc *desc_dev,
+                                    uint32_t first_new, uint32_t m, uint32_t nlist, uint32_t ldc)
+{
+    if (m == 0) return hipSuccess;
+    hipLaunchKernelGGL(coarse_select_kernel, dim3(m), dim3(TRI_SEL_THREADS), 0, c.stream, ws.coarse_scores, ldc,
+                       nlist, desc_dev, first_new, ws.probe, c.nprobe_max);
+    return hipGetLastError();
+}
+
+// ------------------------------------------------------------------------------------------------
+// Slot merge: one workgroup per running slot of the step.  Candidates = the score segments of the
+// slot's work items of this step + its running top-k.  Output = new running top-k, or -- when the
+// slot retires in this step -- its final result record.
+__global__ __launch_bounds__(TRI_SEL_THREADS) void slot_merge_kernel(
+    const TriPlanEntry *__restrict__ plan, const TriSlotMeta *__restrict__ slot_meta,
+    const TriIndexDev *__restrict__ indexes, const uint32_t *__restrict__ item_glist,
+    const uint64_t *__restrict__ item_score_off, const uint32_t *__restrict__ glist_len,
+    const uint32_t *__restrict__ glist_voff, const uint32_t *__restrict__ glist_index,
+    const float *__restrict__ scores, float *__restrict__ topk_score, uint32_t *__restrict__ topk_id,
+    uint32_t *__restrict__ topk_count, uint32_t kmax, uint32_t *__restrict__ res_block,
+    const uint32_t *__restrict__ probe, uint32_t nprobe_max, uint32_t *__restrict__ res_probes)
+{
+    __shared__ SelShared sh;
+    __shared__ uint32_t sh_total;
+    const TriPlanEntry e = plan[blockIdx.x];
+    const TriSlotMeta meta = slot_meta[e.slot];
+    const uint32_t desc = meta.metric == 1u;
+    const uint32_t have = e.cursor > 0 ? topk_count[e.slot] : 0u;
+    float *run_score = topk_score + (size_t)e.slot * kmax;
+    uint32_t *run_id = topk_id + (size_t)e.slot * kmax;
+    const uint32_t nseg = e.take + (have ? 1u : 0u);
+
+    auto seg_of = [&](uint32_t s) {
+        if (s < e.take) {
+            const uint32_t it = e.item_base + s;
+            const uint32_t g = item_glist[it];
+            const TriIndexDev &ix = indexes[glist_index[g]];
+            return SelSeg{scores + item_score_off[it], ix.ids + glist_voff[g], glist_len[g], 0u};
+        }
+        return SelSeg{run_score, run_id, have, 0u};
+    };
+    // total number of candidates
+    if (threadIdx.x == 0) sh_total = have;
+    __syncthreads();
+    uint32_t part = 0;
+    for (uint32_t s = threadIdx.x; s < e.take; s += TRI_SEL_THREADS) part += glist_len[item_glist[e.item_base + s]];
+    if (part) atomicAdd(&sh_total, part);
+    __syncthreads();
+    const uint32_t total = sh_total;
+
+    const uint32_t n = sel_block_topk(sh, nseg, seg_of, total, meta.k, desc);
+    // (all reads of the running buffer are done: sel_block_topk ends with a barrier)
+    if (e.retire_idx >= 0) {
+        uint32_t *rec = res_block + (size_t)e.retire_idx * (1u + 2u * kmax);
+        if (threadIdx.x == 0) rec[0] = n;
+        for (uint32_t i = threadIdx.x; i < n; i += TRI_SEL_THREADS) {
+            const uint64_t c = sh.out[i];
+            rec[1 + i] = (uint32_t)(c & 0xFFFFFFFFu);
+            rec[1 + kmax + i] = __float_as_uint(sel_unkey((uint32_t)(c >> 32), desc));
+        }
+        if (res_probes) {
+            const uint32_t *src = probe + (size_t)e.slot * nprobe_max;
+            uint32_t *dst = res_probes + (size_t)e.retire_idx * nprobe_max;
+            for (uint32_t i = threadIdx.x; i < meta.nprobe; i += TRI_SEL_THREADS) dst[i] = src[i];
+        }
+    } else {
+        for (uint32_t i = threadIdx.x; i < n; i += TRI_SEL_THREADS) {
+            const uint64_t c = sh.out[i];
+            run_id[i] = (uint32_t)(c & 0xFFFFFFFFu);
+            run_score[i] = sel_unkey((uint32_t)(c >> 32), desc);
+        }
+        if (threadIdx.x == 0) topk_count[e.slot] = n;
+    }
+}
+
+hipError_t tri_launch_merge(const TriLaunchCtx &c, const TriDevWs &ws, const TriPlanEntry *plan_dev, uint32_t n_plan,
+                            bool keep_probes)
+{
+    if (n_plan == 0) return hipSuccess;
+    hipLaunchKernelGGL(slot_merge_kernel, dim3(n_plan), dim3(TRI_SEL_THREADS), 0, c.stream, plan_dev, ws.slot_meta,
+                       ws.indexes, ws.item_glist, ws.item_score_off, ws.glist_len, ws.glist_voff, ws.glist_index,
+                       ws.scores, ws.topk_score, ws.topk_id, ws.topk_count, c.kmax, ws.res_block, ws.probe,
+                       c.nprobe_max, keep_probes ? ws.res_probes : (uint32_t *)nullptr);
+    return hipGetLastError();
+}

@@ -1,0 +1,991 @@
+// Host side of the pool worker: C ABI, slot table, class queues, step planner, result delivery.
+// (Paper Sec. 3.2 for the step loop -- admit, emit tasks, one fixed-shape evaluation, merge,
+// retire, recycle -- and Sec. 3.3 for the two priority classes served at step boundaries.)
+#include "../../include/trinity_ivf.h"
+#include "tri_common.h"
+
+#include <algorithm>
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <deque>
+#include <mutex>
+#include <new>
+#include <string>
+#include <vector>
+
+namespace {
+
+thread_local std::string g_err;
+
+int fail(int code, const char *fmt, ...)
+{
+    char buf[512];
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(buf, sizeof buf, fmt, ap);
+    va_end(ap);
+    g_err = buf;
+    return code;
+}
+
+#define HIP_TRY(expr)                                                                          \
+    do {                                                                                       \
+        hipError_t e_ = (expr);                                                                \
+        if (e_ != hipSuccess) return fail(TRI_EHIP, "%s -> %s", #expr, hipGetErrorString(e_)); \
+    } while (0)
+
+constexpr uint32_t RING = 4;          // steps that may be in flight before search_step waits
+constexpr uint32_t N_EV = 6;          // profile events per step
+
+inline uint32_t round_up(uint32_t v, uint32_t m) { return (v + m - 1) / m * m; }
+inline size_t round_up_sz(size_t v, size_t m) { return (v + m - 1) / m * m; }
+inline uint32_t esize(uint32_t dtype) { return dtype == TRI_F16 ? 2u : 4u; }
+inline uint32_t dpad_of(uint32_t dim, uint32_t dtype) { return round_up(dim, 128u / esize(dtype)); }
+
+enum TState : uint8_t { T_FREE = 0, T_PENDING, T_RUNNING, T_RETIRING, T_DONE };
+
+struct Ticket {
+    uint32_t gen = 0;
+    TState state = T_FREE;
+    bool cancelled = false;
+    tri_index *index = nullptr;
+    uint32_t k = 0, nprobe = 0, metric = 0, klass = 0;
+    uint64_t deadline = 0, tag = 0;
+    uint32_t slot = 0;
+    uint64_t step_seq = 0;
+    uint32_t retire_idx = 0;
+    uint32_t n_out = 0;
+};
+
+struct SlotH {
+    bool active = false;
+    uint32_t ticket = 0;
+    uint32_t nprobe = 0, cursor = 0, klass = 0;
+    uint64_t admit_seq = 0;
+    tri_index *index = nullptr;
+};
+
+struct StepRec {
+    bool in_use = false;
+    bool profiled = false;
+    uint64_t seq = 0;
+    hipEvent_t done = nullptr;
+    hipEvent_t ev[N_EV] = {};
+    uint8_t *up_host = nullptr;       // pinned: upload block
+    uint8_t *down_host = nullptr;     // pinned: result block, probes, step numbers
+    std::vector<uint32_t> retire;     // ticket index per retire_idx
+    uint32_t n_items = 0;
+    bool had_scan = false;
+};
+
+}  // namespace
+
+struct tri_index {
+    tri_pool *pool = nullptr;
+    uint32_t id = 0;
+    ivf_params p{};
+    uint64_t n = 0;
+    uint32_t dpad = 0, row_bytes = 0, list_base = 0, max_list_len = 0;
+    TriIndexDev dev{};
+    uint32_t *ids_dev = nullptr;
+    uint32_t *list_off_dev = nullptr;
+};
+
+struct tri_pool {
+    tri_pool_cfg cfg{};
+    int device = 0;
+    hipStream_t stream = nullptr;
+    std::mutex mu;
+    TriDevWs ws{};
+    TriLaunchCtx ctx{};
+    uint32_t max_row_bytes = 0, coarse_rows = 0, coarse_ldc = 0;
+    uint32_t attached_row_bytes = 128;   // widest row among the attached indexes (sizes the scan kernel's LDS)
+    uint64_t score_capacity = 0;
+    size_t upload_bytes = 0, down_bytes = 0;
+    size_t down_probe_off = 0, down_step_off = 0;
+    // indexes
+    std::vector<tri_index *> indexes;
+    uint32_t total_lists = 0;
+    // tickets
+    std::vector<Ticket> tickets;
+    std::vector<uint32_t> free_tickets;
+    std::vector<uint8_t> qstore;       // [max_outstanding][max_row_bytes] padded query rows
+    std::vector<uint32_t> res_ids;     // [max_outstanding][kmax]
+    std::vector<float> res_score;      // [max_outstanding][kmax]
+    std::vector<uint32_t> res_probe;   // [max_outstanding][nprobe_max] (only with KEEP_PROBES)
+    std::deque<uint32_t> pending[2];
+    // slots
+    std::vector<SlotH> slots;
+    std::vector<uint32_t> free_slots;
+    uint32_t n_running = 0;
+    uint64_t admit_seq = 0, step_seq = 0;
+    StepRec ring[RING];
+    uint8_t *pinned = nullptr;
+    tri_kernel_times times{};
+    // scratch vectors reused by search_step
+    std::vector<uint32_t> order, newq;
+};
+
+namespace {
+
+// Carve the device workspace.  Must match TriDevWs field for field.
+size_t carve(const tri_pool_cfg &c, uint32_t max_row_bytes, uint32_t coarse_rows, uint32_t coarse_ldc,
+             uint64_t score_capacity, size_t upload_bytes, uint8_t *base, TriDevWs *ws)
+{
+    size_t o = 0;
+    auto take = [&](size_t bytes) {
+        size_t at = o;
+        o = round_up_sz(o + bytes, 256);
+        return base ? base + at : (uint8_t *)nullptr;
+    };
+    const size_t S = c.slots, W = c.items_per_step, G = (size_t)c.max_total_lists + 1;
+    uint8_t *p;
+#define CARVE(field, type, bytes) p = take(bytes); if (ws) ws->field = (type)p;
+    CARVE(slot_query, uint8_t *, S * max_row_bytes)
+    CARVE(slot_meta, TriSlotMeta *, S * sizeof(TriSlotMeta))
+    CARVE(slot_qnorm, float *, S * 4)
+    CARVE(probe, uint32_t *, S * c.nprobe_max * 4)
+    CARVE(topk_score, float *, S * c.kmax * 4)
+    CARVE(topk_id, uint32_t *, S * c.kmax * 4)
+    CARVE(topk_count, uint32_t *, S * 4)
+    CARVE(indexes, TriIndexDev *, (size_t)c.max_indexes * sizeof(TriIndexDev))
+    CARVE(glist_len, uint32_t *, G * 4)
+    CARVE(glist_voff, uint32_t *, G * 4)
+    CARVE(glist_index, uint32_t *, G * 4)
+    CARVE(upload, uint8_t *, upload_bytes)
+    CARVE(coarse_scores, float *, (size_t)coarse_rows * coarse_ldc * 4)
+    CARVE(item_glist, uint32_t *, W * 4)
+    CARVE(item_slot, uint32_t *, W * 4)
+    CARVE(item_rank, uint32_t *, W * 4)
+    CARVE(item_score_off, uint64_t *, W * 8)
+    CARVE(sorted_slot, uint32_t *, W * 4)
+    CARVE(hist, uint32_t *, G * 4)
+    CARVE(list_start, uint32_t *, G * 4)
+    CARVE(tile_base, uint32_t *, G * 4)
+    CARVE(score_base, uint64_t *, G * 8)
+    CARVE(tiles, TriTile *, W * sizeof(TriTile))
+    CARVE(tile_counter, uint32_t *, 256)
+    CARVE(step_dev, TriStepDev *, 256)
+    CARVE(scores, float *, (size_t)score_capacity * 4)
+    CARVE(res_block, uint32_t *, S * (1 + 2 * (size_t)c.kmax) * 4)
+    CARVE(res_probes, uint32_t *, S * (size_t)c.nprobe_max * 4)
+#undef CARVE
+    return o;
+}
+
+int derive(const tri_pool_cfg *c, uint32_t *max_row_bytes, uint32_t *coarse_rows, uint32_t *coarse_ldc,
+           uint64_t *score_capacity, size_t *upload_bytes)
+{
+    if (!c) return fail(TRI_EINVAL, "cfg is NULL");
+    if (c->slots == 0 || c->slots > (1u << 20)) return fail(TRI_EINVAL, "slots must be 1..2^20");
+    if (c->items_per_step == 0) return fail(TRI_EINVAL, "items_per_step must be > 0");
+    if (c->kmax == 0 || c->kmax > TRI_KMAX_LIMIT) return fail(TRI_EINVAL, "kmax must be 1..%u", TRI_KMAX_LIMIT);
+    if (c->nprobe_max == 0 || c->nprobe_max > TRI_NPROBE_LIMIT)
+        return fail(TRI_EINVAL, "nprobe_max must be 1..%u", TRI_NPROBE_LIMIT);
+    if (c->max_indexes == 0 || c->max_indexes > 256) return fail(TRI_EINVAL, "max_indexes must be 1..256");
+    if (c->max_nlist == 0 || c->max_total_lists < c->max_nlist)
+        return fail(TRI_EINVAL, "need 0 < max_nlist <= max_total_lists");
+    if (c->max_dim == 0) return fail(TRI_EINVAL, "max_dim must be > 0");
+    if (c->max_outstanding < c->slots) return fail(TRI_EINVAL, "max_outstanding must be >= slots");
+    const uint32_t rb = round_up(c->max_dim * 4u, 128u);   // fp32 rows are the widest
+    const uint32_t rb16 = round_up(c->max_dim * 2u, 128u);
+    if (rb16 > TRI_MAX_ROW_BYTES) return fail(TRI_EINVAL, "max_dim too large: padded fp16 row exceeds %u bytes", TRI_MAX_ROW_BYTES);
+    *max_row_bytes = rb > TRI_MAX_ROW_BYTES ? TRI_MAX_ROW_BYTES : rb;
+    *coarse_rows = c->coarse_rows ? c->coarse_rows : 1024u;
+    if (*coarse_rows > c->slots) *coarse_rows = c->slots;
+    *coarse_ldc = round_up(c->max_nlist, 32u);
+    *score_capacity = c->score_capacity ? c->score_capacity : (uint64_t)c->items_per_step * 1024u;
+    *upload_bytes = round_up_sz((size_t)c->slots * sizeof(TriNewDesc), 256) +
+                    round_up_sz((size_t)c->slots * sizeof(TriPlanEntry), 256) + (size_t)c->slots * *max_row_bytes;
+    return TRI_OK;
+}
+
+// Deliver the results of every completed step (oldest first).  block: wait for all of them.
+int reap(tri_pool *P, bool block, uint32_t *finished)
+{
+    uint32_t fin = 0;
+    // oldest in-use entry first
+    for (uint32_t n = 0; n < RING; ++n) {
+        StepRec *R = nullptr;
+        for (uint32_t i = 0; i < RING; ++i)
+            if (P->ring[i].in_use && (!R || P->ring[i].seq < R->seq)) R = &P->ring[i];
+        if (!R) break;
+        if (block) {
+            HIP_TRY(hipEventSynchronize(R->done));
+        } else {
+            hipError_t q = hipEventQuery(R->done);
+            if (q == hipErrorNotReady) break;
+            if (q != hipSuccess) return fail(TRI_EHIP, "hipEventQuery -> %s", hipGetErrorString(q));
+        }
+        const uint32_t kmax = P->cfg.kmax, pmax = P->cfg.nprobe_max;
+        const uint32_t *blk = (const uint32_t *)R->down_host;
+        const uint32_t *prb = (const uint32_t *)(R->down_host + P->down_probe_off);
+        for (size_t i = 0; i < R->retire.size(); ++i) {
+            const uint32_t ti = R->retire[i];
+            Ticket &t = P->tickets[ti];
+            if (t.cancelled) {
+                t.state = T_FREE;
+                t.cancelled = false;
+                ++t.gen;
+                P->free_tickets.push_back(ti);
+                continue;
+            }
+            const uint32_t *rec = blk + i * (1 + 2 * (size_t)kmax);
+            t.n_out = rec[0];
+            memcpy(&P->res_ids[(size_t)ti * kmax], rec + 1, (size_t)t.n_out * 4);
+            memcpy(&P->res_score[(size_t)ti * kmax], rec + 1 + kmax, (size_t)t.n_out * 4);
+            if (P->cfg.flags & TRI_FLAG_KEEP_PROBES)
+                memcpy(&P->res_probe[(size_t)ti * pmax], prb + i * (size_t)pmax, (size_t)t.nprobe * 4);
+            t.state = T_DONE;
+            ++fin;
+        }
+        if (R->profiled) {
+            float ms[N_EV - 1] = {};
+            for (uint32_t i = 0; i + 1 < N_EV; ++i) HIP_TRY(hipEventElapsedTime(&ms[i], R->ev[i], R->ev[i + 1]));
+            const TriStepDev *sd = (const TriStepDev *)(R->down_host + P->down_step_off);
+            P->times.steps += 1;
+            P->times.admit_ms += ms[0];
+            P->times.coarse_ms += ms[1];
+            P->times.pack_ms += ms[2];
+            P->times.scan_ms += ms[3];
+            P->times.select_ms += ms[4];
+            if (R->had_scan) {
+                P->times.scan_launches += 1;
+                P->times.scan_vector_bytes += sd->tile_vec_bytes;
+                P->times.scan_unique_bytes += sd->unique_vec_bytes;
+                P->times.scan_items += R->n_items;
+            }
+        }
+        R->retire.clear();
+        R->in_use = false;
+    }
+    if (finished) *finished += fin;
+    return TRI_OK;
+}
+
+bool ticket_lookup(tri_pool *P, tri_ticket t, uint32_t *idx)
+{
+    const uint32_t i = (uint32_t)(t & 0xFFFFFFFFull), gen = (uint32_t)(t >> 32);
+    if (i >= P->tickets.size()) return false;
+    if (P->tickets[i].gen != gen || P->tickets[i].state == T_FREE) return false;
+    *idx = i;
+    return true;
+}
+
+int validate_query(tri_pool *P, const tri_query *q)
+{
+    if (!q->index || q->index->pool != P) return fail(TRI_EINVAL, "query.index is not attached to this pool");
+    if (!q->vec) return fail(TRI_EINVAL, "query.vec is NULL");
+    if (q->k == 0 || q->k > P->cfg.kmax) return fail(TRI_EINVAL, "k=%u outside 1..%u", q->k, P->cfg.kmax);
+    if (q->nprobe == 0 || q->nprobe > P->cfg.nprobe_max || q->nprobe > q->index->p.nlist)
+        return fail(TRI_EINVAL, "nprobe=%u outside 1..min(%u, nlist=%u)", q->nprobe, P->cfg.nprobe_max, q->index->p.nlist);
+    if (q->metric != TRI_L2 && q->metric != TRI_IP) return fail(TRI_EINVAL, "metric must be TRI_L2 or TRI_IP");
+    if (q->klass != TRI_CLASS_HIGH && q->klass != TRI_CLASS_LOW) return fail(TRI_EINVAL, "klass must be TRI_CLASS_HIGH or TRI_CLASS_LOW");
+    return TRI_OK;
+}
+
+void enqueue_locked(tri_pool *P, const tri_query *q, tri_ticket *out)
+{
+    const uint32_t ti = P->free_tickets.back();
+    P->free_tickets.pop_back();
+    Ticket &t = P->tickets[ti];
+    t.state = T_PENDING;
+    t.cancelled = false;
+    t.index = const_cast<tri_index *>(q->index);
+    t.k = q->k; t.nprobe = q->nprobe; t.metric = q->metric; t.klass = q->klass;
+    t.deadline = q->deadline_ns; t.tag = q->user_tag;
+    uint8_t *row = &P->qstore[(size_t)ti * P->max_row_bytes];
+    const uint32_t es = esize(t.index->p.dtype);
+    memcpy(row, q->vec, (size_t)t.index->p.dim * es);
+    memset(row + (size_t)t.index->p.dim * es, 0, t.index->row_bytes - (size_t)t.index->p.dim * es);
+    P->pending[t.klass].push_back(ti);
+    *out = ((uint64_t)t.gen << 32) | ti;
+}
+
+}  // namespace
+
+// ================================================================================== pool
+extern "C" int tri_pool_workspace_bytes(const tri_pool_cfg *cfg, size_t *dev_bytes)
+{
+    uint32_t mrb, cr, ldc;
+    uint64_t sc;
+    size_t up;
+    int rc = derive(cfg, &mrb, &cr, &ldc, &sc, &up);
+    if (rc) return rc;
+    if (!dev_bytes) return fail(TRI_EINVAL, "dev_bytes is NULL");
+    *dev_bytes = carve(*cfg, mrb, cr, ldc, sc, up, nullptr, nullptr);
+    return TRI_OK;
+}
+
+extern "C" int tri_pool_create(const tri_pool_cfg *cfg, void *dev_ws, size_t dev_ws_bytes, tri_pool **out)
+{
+    uint32_t mrb, cr, ldc;
+    uint64_t sc;
+    size_t up;
+    int rc = derive(cfg, &mrb, &cr, &ldc, &sc, &up);
+    if (rc) return rc;
+    if (!dev_ws || !out) return fail(TRI_EINVAL, "dev_ws / out is NULL");
+    if ((uintptr_t)dev_ws % 256) return fail(TRI_EINVAL, "dev_ws must be 256-byte aligned");
+    const size_t need = carve(*cfg, mrb, cr, ldc, sc, up, nullptr, nullptr);
+    if (dev_ws_bytes < need) return fail(TRI_ENOMEM, "dev_ws has %zu bytes, %zu needed", dev_ws_bytes, need);
+    int ndev = 0;
+    if (hipGetDeviceCount(&ndev) != hipSuccess || ndev == 0) return fail(TRI_EHIP, "no HIP device");
+    tri_pool *P = new (std::nothrow) tri_pool();
+    if (!P) return fail(TRI_ENOMEM, "out of host memory");
+    P->cfg = *cfg;
+    hipError_t e = hipGetDevice(&P->device);
+    hipDeviceProp_t prop;
+    if (e == hipSuccess) e = hipGetDeviceProperties(&prop, P->device);
+    if (e != hipSuccess) { delete P; return fail(TRI_EHIP, "device query -> %s", hipGetErrorString(e)); }
+    P->stream = (hipStream_t)cfg->hip_stream;
+    P->max_row_bytes = mrb; P->coarse_rows = cr; P->coarse_ldc = ldc; P->score_capacity = sc; P->upload_bytes = up;
+    carve(*cfg, mrb, cr, ldc, sc, up, (uint8_t *)dev_ws, &P->ws);
+    P->ctx = TriLaunchCtx{P->stream, cfg->slots, cfg->items_per_step, cfg->kmax, cfg->nprobe_max,
+                          cfg->max_total_lists, mrb, (uint32_t)prop.multiProcessorCount};
+    // pinned staging for RING steps
+    const size_t S = cfg->slots;
+    const size_t blk = round_up_sz(S * (1 + 2 * (size_t)cfg->kmax) * 4, 256);
+    const size_t prb = round_up_sz(S * (size_t)cfg->nprobe_max * 4, 256);
+    P->down_probe_off = blk;
+    P->down_step_off = blk + prb;
+    P->down_bytes = blk + prb + 256;
+    const size_t per = round_up_sz(up, 256) + P->down_bytes;
+    e = hipHostMalloc((void **)&P->pinned, per * RING, hipHostMallocDefault);
+    if (e != hipSuccess) { delete P; return fail(TRI_EHIP, "hipHostMalloc(%zu) -> %s", per * RING, hipGetErrorString(e)); }
+    for (uint32_t i = 0; i < RING; ++i) {
+        StepRec &R = P->ring[i];
+        R.up_host = P->pinned + i * per;
+        R.down_host = R.up_host + round_up_sz(up, 256);
+        e = hipEventCreateWithFlags(&R.done, hipEventDisableTiming);
+        for (uint32_t j = 0; j < N_EV && e == hipSuccess; ++j) e = hipEventCreate(&R.ev[j]);
+        if (e != hipSuccess) { tri_pool_destroy(P); return fail(TRI_EHIP, "hipEventCreate -> %s", hipGetErrorString(e)); }
+    }
+    try {
+        P->tickets.resize(cfg->max_outstanding);
+        P->free_tickets.reserve(cfg->max_outstanding);
+        for (uint32_t i = cfg->max_outstanding; i-- > 0;) P->free_tickets.push_back(i);
+        P->qstore.resize((size_t)cfg->max_outstanding * mrb);
+        P->res_ids.resize((size_t)cfg->max_outstanding * cfg->kmax);
+        P->res_score.resize((size_t)cfg->max_outstanding * cfg->kmax);
+        if (cfg->flags & TRI_FLAG_KEEP_PROBES) P->res_probe.resize((size_t)cfg->max_outstanding * cfg->nprobe_max);
+        P->slots.resize(S);
+        P->free_slots.reserve(S);
+        for (uint32_t i = (uint32_t)S; i-- > 0;) P->free_slots.push_back(i);
+        P->indexes.assign(cfg->max_indexes, nullptr);
+        P->order.reserve(S);
+        P->newq.reserve(S);
+    } catch (const std::bad_alloc &) {
+        tri_pool_destroy(P);
+        return fail(TRI_ENOMEM, "out of host memory");
+    }
+    e = tri_scan_configure(mrb);
+    if (e != hipSuccess) { tri_pool_destroy(P); return fail(TRI_EHIP, "scan kernel LDS limit -> %s", hipGetErrorString(e)); }
+    *out = P;
+    return TRI_OK;
+}
+
+extern "C" int tri_pool_destroy(tri_pool *P)
+{
+    if (!P) return fail(TRI_EINVAL, "pool is NULL");
+    for (tri_index *ix : P->indexes)
+        if (ix) return fail(TRI_EINVAL, "destroy the pool's indexes first");
+    (void)hipStreamSynchronize(P->stream);
+    for (uint32_t i = 0; i < RING; ++i) {
+        if (P->ring[i].done) (void)hipEventDestroy(P->ring[i].done);
+        for (uint32_t j = 0; j < N_EV; ++j)
+            if (P->ring[i].ev[j]) (void)hipEventDestroy(P->ring[i].ev[j]);
+    }
+    if (P->pinned) (void)hipHostFree(P->pinned);
+    delete P;
+    return TRI_OK;
+}
+
+// ================================================================================== index
+extern "C" int ivf_build_bytes(const ivf_params *p, uint64_t n, size_t *dev_bytes)
+{
+    if (!p || !dev_bytes) return fail(TRI_EINVAL, "NULL argument");
+    if (p->dtype != TRI_F32 && p->dtype != TRI_F16) return fail(TRI_EINVAL, "dtype must be TRI_F32 or TRI_F16");
+    if (p->dim == 0 || p->nlist == 0 || n == 0) return fail(TRI_EINVAL, "dim, nlist and n must be > 0");
+    if (n >= (1ull << 32)) return fail(TRI_EINVAL, "n must be < 2^32");
+    if (p->nlist > n) return fail(TRI_EINVAL, "nlist > n");
+    const uint32_t dpad = dpad_of(p->dim, p->dtype), rb = dpad * esize(p->dtype);
+    if (rb > TRI_MAX_ROW_BYTES) return fail(TRI_EINVAL, "padded row of %u bytes exceeds %u", rb, TRI_MAX_ROW_BYTES);
+    size_t o = 0;
+    o += round_up_sz((size_t)n * rb, 256);                 // vectors
+    o += round_up_sz(((size_t)n + TRI_VB) * 4, 256);       // |x|^2 (+ one block of slack for tail reads)
+    o += round_up_sz((size_t)n * 4, 256);                  // ids
+    o += round_up_sz(((size_t)p->nlist + 1) * 4, 256);     // list offsets
+    o += round_up_sz((size_t)p->nlist * rb, 256);          // centroids
+    o += round_up_sz((size_t)p->nlist * 4, 256);           // |c|^2
+    *dev_bytes = o;
+    return TRI_OK;
+}
+
+namespace {
+struct TmpMem {      // frees its device allocations on scope exit
+    std::vector<void *> ptrs;
+    ~TmpMem() { for (void *p : ptrs) (void)hipFree(p); }
+    hipError_t alloc(void **p, size_t bytes)
+    {
+        hipError_t e = hipMalloc(p, bytes ? bytes : 256);
+        if (e == hipSuccess) ptrs.push_back(*p);
+        return e;
+    }
+};
+
+uint64_t splitmix64(uint64_t &s)
+{
+    uint64_t z = (s += 0x9E3779B97F4A7C15ull);
+    z = (z ^ (z >> 30)) * 0xBF58476D1CE4E5B9ull;
+    z = (z ^ (z >> 27)) * 0x94D049BB133111EBull;
+    return z ^ (z >> 31);
+}
+uint64_t gcd64(uint64_t a, uint64_t b) { while (b) { uint64_t t = a % b; a = b; b = t; } return a; }
+
+// Assign rows [0, nrows) of `rows_of(chunk)` to their best centroid, chunk by chunk.
+int assign_all(hipStream_t s, int dtype, uint32_t dim, uint32_t dpad, uint32_t rb, const void *base, uint64_t base_pitch,
+               const void *padded_or_null, uint64_t nrows, const void *cent, const float *cnorm, uint32_t nlist,
+               int metric, void *chunk_rows, float *scores, uint32_t ldc, uint32_t chunk, uint32_t *assign)
+{
+    for (uint64_t r0 = 0; r0 < nrows; r0 += chunk) {
+        const uint32_t m = (uint32_t)std::min<uint64_t>(chunk, nrows - r0);
+        const void *a_rows;
+        if (padded_or_null) {
+            a_rows = (const uint8_t *)padded_or_null + r0 * rb;
+        } else {
+            HIP_TRY(tri_build_pad_rows(s, dtype, base, dim, base_pitch, nullptr, 1, r0, ~0ull, m, chunk_rows, dpad));
+            a_rows = chunk_rows;
+        }
+        HIP_TRY(tri_launch_coarse_gemm(s, dtype, a_rows, rb, m, cent, cnorm, nlist, rb, nullptr, 0, (uint32_t)metric,
+                                       scores, ldc));
+        HIP_TRY(tri_build_argbest(s, scores, ldc, m, nlist, metric, assign + r0));
+    }
+    return TRI_OK;
+}
+}  // namespace
+
+extern "C" int ivf_build(tri_pool *P, const ivf_params *p, const void *base, uint64_t n, const float *centroids,
+                         void *dev_mem, size_t dev_mem_bytes, tri_index **out)
+{
+    if (!P || !p || !base || !dev_mem || !out) return fail(TRI_EINVAL, "NULL argument");
+    size_t need = 0;
+    int rc = ivf_build_bytes(p, n, &need);
+    if (rc) return rc;
+    if (p->build_metric != TRI_L2 && p->build_metric != TRI_IP) return fail(TRI_EINVAL, "build_metric must be TRI_L2 or TRI_IP");
+    if ((uintptr_t)dev_mem % 256) return fail(TRI_EINVAL, "dev_mem must be 256-byte aligned");
+    if (dev_mem_bytes < need) return fail(TRI_ENOMEM, "dev_mem has %zu bytes, %zu needed", dev_mem_bytes, need);
+    std::lock_guard<std::mutex> lk(P->mu);
+    if (p->dim > P->cfg.max_dim) return fail(TRI_EINVAL, "dim %u > pool max_dim %u", p->dim, P->cfg.max_dim);
+    if (p->nlist > P->cfg.max_nlist) return fail(TRI_EINVAL, "nlist %u > pool max_nlist %u", p->nlist, P->cfg.max_nlist);
+    if ((uint64_t)P->total_lists + p->nlist > P->cfg.max_total_lists)
+        return fail(TRI_ENOMEM, "pool list table full (%u + %u > %u)", P->total_lists, p->nlist, P->cfg.max_total_lists);
+    if (P->n_running || !P->pending[0].empty() || !P->pending[1].empty())
+        return fail(TRI_EINVAL, "ivf_build while queries are queued or running");
+    uint32_t id = 0;
+    while (id < P->cfg.max_indexes && P->indexes[id]) ++id;
+    if (id == P->cfg.max_indexes) return fail(TRI_ENOMEM, "pool already holds max_indexes=%u indexes", P->cfg.max_indexes);
+    rc = reap(P, true, nullptr);
+    if (rc) return rc;
+    HIP_TRY(hipSetDevice(P->device));
+    hipStream_t s = P->stream;
+    HIP_TRY(hipStreamSynchronize(s));
+
+    const int dtype = (int)p->dtype, metric = (int)p->build_metric;
+    const uint32_t es = esize(p->dtype), dim = p->dim, nlist = p->nlist;
+    const uint32_t dpad = dpad_of(dim, p->dtype), rb = dpad * es;
+    if (rb > P->max_row_bytes) return fail(TRI_EINVAL, "padded row %u bytes > pool row %u bytes", rb, P->max_row_bytes);
+
+    // carve dev_mem
+    uint8_t *m = (uint8_t *)dev_mem;
+    uint8_t *vecs = m;              m += round_up_sz((size_t)n * rb, 256);
+    float *vnorm = (float *)m;      m += round_up_sz(((size_t)n + TRI_VB) * 4, 256);
+    uint32_t *ids = (uint32_t *)m;  m += round_up_sz((size_t)n * 4, 256);
+    uint32_t *loff = (uint32_t *)m; m += round_up_sz(((size_t)nlist + 1) * 4, 256);
+    uint8_t *cent = m;              m += round_up_sz((size_t)nlist * rb, 256);
+    float *cnorm = (float *)m;
+
+    TmpMem tmp;
+    // base on the device
+    const void *dbase = base;
+    hipPointerAttribute_t attr;
+    bool on_device = false;
+    if (hipPointerGetAttributes(&attr, base) == hipSuccess)
+        on_device = attr.type == hipMemoryTypeDevice || attr.type == hipMemoryTypeManaged;
+    else
+        (void)hipGetLastError();     // plain host memory: the query itself reports an error
+    if (!on_device) {
+        void *d = nullptr;
+        HIP_TRY(tmp.alloc(&d, (size_t)n * dim * es));
+        HIP_TRY(hipMemcpy(d, base, (size_t)n * dim * es, hipMemcpyHostToDevice));
+        dbase = d;
+    }
+    // working buffers
+    float *cent_f32 = nullptr;
+    HIP_TRY(tmp.alloc((void **)&cent_f32, (size_t)nlist * dpad * 4));
+    const uint32_t ldc = round_up(nlist, 32);
+    uint32_t chunk = (uint32_t)std::min<uint64_t>(n, std::max<uint64_t>(128, (256ull << 20) / ldc));
+    chunk = round_up(chunk, 128);
+    float *scores = nullptr;
+    void *chunk_rows = nullptr;
+    uint32_t *assign = nullptr, *block_hist = nullptr, *list_len = nullptr;
+    HIP_TRY(tmp.alloc((void **)&scores, (size_t)chunk * ldc * 4));
+    HIP_TRY(tmp.alloc(&chunk_rows, (size_t)chunk * rb));
+    HIP_TRY(tmp.alloc((void **)&assign, (size_t)n * 4));
+    const uint32_t nblocks = (uint32_t)std::min<uint64_t>(512, (n + 255) / 256);
+    HIP_TRY(tmp.alloc((void **)&block_hist, (size_t)nblocks * nlist * 4));
+    HIP_TRY(tmp.alloc((void **)&list_len, (size_t)nlist * 4));
+
+    // ---- initial centroids
+    if (centroids) {
+        std::vector<float> padded((size_t)nlist * dpad, 0.f);
+        for (uint32_t l = 0; l < nlist; ++l) memcpy(&padded[(size_t)l * dpad], centroids + (size_t)l * dim, (size_t)dim * 4);
+        HIP_TRY(hipMemcpy(cent_f32, padded.data(), padded.size() * 4, hipMemcpyHostToDevice));
+    } else {
+        // nlist distinct rows: an affine map j -> (a*j + b) mod n with gcd(a, n) = 1 is a permutation
+        uint64_t st = p->seed, a = splitmix64(st) % n, b = splitmix64(st) % n;
+        if (a == 0) a = 1;
+        while (gcd64(a, n) != 1) a = a % n + 1;
+        HIP_TRY(tri_build_pad_rows(s, dtype, dbase, dim, dim, nullptr, a, b, n, nlist, cent, dpad));
+        HIP_TRY(tri_build_widen_rows(s, dtype, cent, (uint64_t)nlist * dpad, cent_f32));
+    }
+
+    // ---- Lloyd iterations on the training rows
+    if (p->train_iters) {
+        const uint64_t ns = n <= 256ull * nlist ? n : 256ull * nlist;
+        void *train = nullptr;
+        uint32_t *perm_s = nullptr, *loff_s = nullptr;
+        HIP_TRY(tmp.alloc(&train, (size_t)ns * rb));
+        HIP_TRY(tmp.alloc((void **)&perm_s, (size_t)ns * 4));
+        HIP_TRY(tmp.alloc((void **)&loff_s, ((size_t)nlist + 1) * 4));
+        uint64_t a = 1, b = 0;
+        if (ns < n) {
+            uint64_t st = p->seed ^ 0x7472696e69747921ull;
+            a = splitmix64(st) % n; b = splitmix64(st) % n;
+            if (a == 0) a = 1;
+            while (gcd64(a, n) != 1) a = a % n + 1;
+        }
+        for (uint64_t r0 = 0; r0 < ns; r0 += (1u << 20)) {   // (a*(r0+i) + b) mod n, a million rows per launch
+            const uint64_t cnt = std::min<uint64_t>(1u << 20, ns - r0);
+            HIP_TRY(tri_build_pad_rows(s, dtype, dbase, dim, dim, nullptr, a, (a * r0 + b) % n, n, cnt,
+                                       (uint8_t *)train + r0 * rb, dpad));
+        }
+        const uint32_t nb_s = (uint32_t)std::min<uint64_t>(512, (ns + 255) / 256);
+        for (uint32_t it = 0; it < p->train_iters; ++it) {
+            HIP_TRY(tri_build_convert_centroids(s, dtype, cent_f32, nlist, dpad, cent));
+            HIP_TRY(tri_build_row_norms(s, dtype, cent, dpad, nlist, cnorm));
+            rc = assign_all(s, dtype, dim, dpad, rb, nullptr, 0, train, ns, cent, cnorm, nlist, metric, chunk_rows,
+                            scores, ldc, chunk, assign);
+            if (rc) return rc;
+            HIP_TRY(tri_build_partition(s, assign, ns, nlist, block_hist, nb_s, list_len, loff_s, perm_s));
+            HIP_TRY(tri_build_cluster_means(s, dtype, train, dpad, loff_s, perm_s, nlist, metric == TRI_IP, cent_f32));
+        }
+    }
+
+    // ---- final centroids, assignment of every row, list-major store
+    HIP_TRY(tri_build_convert_centroids(s, dtype, cent_f32, nlist, dpad, cent));
+    HIP_TRY(tri_build_row_norms(s, dtype, cent, dpad, nlist, cnorm));
+    rc = assign_all(s, dtype, dim, dpad, rb, dbase, dim, nullptr, n, cent, cnorm, nlist, metric, chunk_rows, scores,
+                    ldc, chunk, assign);
+    if (rc) return rc;
+    HIP_TRY(tri_build_partition(s, assign, n, nlist, block_hist, nblocks, list_len, loff, ids));
+    for (uint64_t r0 = 0; r0 < n; r0 += (1u << 20)) {
+        const uint64_t cnt = std::min<uint64_t>(1u << 20, n - r0);
+        HIP_TRY(tri_build_pad_rows(s, dtype, dbase, dim, dim, ids + r0, 0, 0, 1, cnt, vecs + r0 * rb, dpad));
+    }
+    HIP_TRY(tri_build_row_norms(s, dtype, vecs, dpad, n, vnorm));
+    HIP_TRY(tri_launch_fill_u32(s, (uint32_t *)(vnorm + n), 0u, TRI_VB));
+    HIP_TRY(hipStreamSynchronize(s));
+
+    // ---- attach
+    std::vector<uint32_t> h_off((size_t)nlist + 1);
+    HIP_TRY(hipMemcpy(h_off.data(), loff, h_off.size() * 4, hipMemcpyDeviceToHost));
+    if (h_off[nlist] != n) return fail(TRI_EHIP, "partition produced %u rows, expected %llu", h_off[nlist], (unsigned long long)n);
+    uint32_t maxlen = 0;
+    std::vector<uint32_t> h_len(nlist), h_idx(nlist, id);
+    for (uint32_t l = 0; l < nlist; ++l) { h_len[l] = h_off[l + 1] - h_off[l]; maxlen = std::max(maxlen, h_len[l]); }
+    if ((uint64_t)round_up(maxlen, TRI_VB) > P->score_capacity)
+        return fail(TRI_ENOMEM, "longest list (%u) exceeds the pool's score capacity", maxlen);
+    tri_index *ix = new (std::nothrow) tri_index();
+    if (!ix) return fail(TRI_ENOMEM, "out of host memory");
+    ix->pool = P; ix->id = id; ix->p = *p; ix->n = n; ix->dpad = dpad; ix->row_bytes = rb;
+    ix->list_base = P->total_lists; ix->max_list_len = maxlen; ix->ids_dev = ids; ix->list_off_dev = loff;
+    ix->dev = TriIndexDev{vecs, vnorm, ids, loff, cent, cnorm, dim, dpad, nlist, p->dtype, rb, ix->list_base, maxlen, 0, n};
+    hipError_t e = hipMemcpy(P->ws.indexes + id, &ix->dev, sizeof(TriIndexDev), hipMemcpyHostToDevice);
+    if (e == hipSuccess) e = hipMemcpy(P->ws.glist_len + ix->list_base, h_len.data(), (size_t)nlist * 4, hipMemcpyHostToDevice);
+    if (e == hipSuccess) e = hipMemcpy(P->ws.glist_voff + ix->list_base, h_off.data(), (size_t)nlist * 4, hipMemcpyHostToDevice);
+    if (e == hipSuccess) e = hipMemcpy(P->ws.glist_index + ix->list_base, h_idx.data(), (size_t)nlist * 4, hipMemcpyHostToDevice);
+    if (e != hipSuccess) { delete ix; return fail(TRI_EHIP, "attach copy -> %s", hipGetErrorString(e)); }
+    P->indexes[id] = ix;
+    P->total_lists += nlist;
+    P->attached_row_bytes = std::max(P->attached_row_bytes, rb);
+    *out = ix;
+    return TRI_OK;
+}
+
+extern "C" int ivf_export(const tri_index *ix, float *centroids, uint64_t *list_off, int64_t *list_ids)
+{
+    if (!ix) return fail(TRI_EINVAL, "index is NULL");
+    HIP_TRY(hipSetDevice(ix->pool->device));
+    HIP_TRY(hipStreamSynchronize(ix->pool->stream));
+    const uint32_t nlist = ix->p.nlist, dim = ix->p.dim;
+    if (centroids) {
+        std::vector<uint8_t> raw((size_t)nlist * ix->row_bytes);
+        HIP_TRY(hipMemcpy(raw.data(), ix->dev.centroids, raw.size(), hipMemcpyDeviceToHost));
+        for (uint32_t l = 0; l < nlist; ++l) {
+            const uint8_t *row = raw.data() + (size_t)l * ix->row_bytes;
+            for (uint32_t i = 0; i < dim; ++i)
+                centroids[(size_t)l * dim + i] = ix->p.dtype == TRI_F16 ? (float)((const _Float16 *)row)[i] : ((const float *)row)[i];
+        }
+    }
+    if (list_off) {
+        std::vector<uint32_t> h((size_t)nlist + 1);
+        HIP_TRY(hipMemcpy(h.data(), ix->list_off_dev, h.size() * 4, hipMemcpyDeviceToHost));
+        for (size_t i = 0; i < h.size(); ++i) list_off[i] = h[i];
+    }
+    if (list_ids) {
+        std::vector<uint32_t> h((size_t)ix->n);
+        HIP_TRY(hipMemcpy(h.data(), ix->ids_dev, h.size() * 4, hipMemcpyDeviceToHost));
+        for (size_t i = 0; i < h.size(); ++i) list_ids[i] = (int64_t)h[i];
+    }
+    return TRI_OK;
+}
+
+extern "C" int ivf_info(const tri_index *ix, uint64_t *n, uint32_t *dim, uint32_t *nlist, uint32_t *dtype,
+                        uint32_t *max_list_len)
+{
+    if (!ix) return fail(TRI_EINVAL, "index is NULL");
+    if (n) *n = ix->n;
+    if (dim) *dim = ix->p.dim;
+    if (nlist) *nlist = ix->p.nlist;
+    if (dtype) *dtype = ix->p.dtype;
+    if (max_list_len) *max_list_len = ix->max_list_len;
+    return TRI_OK;
+}
+
+extern "C" int ivf_destroy(tri_index *ix)
+{
+    if (!ix) return fail(TRI_EINVAL, "index is NULL");
+    tri_pool *P = ix->pool;
+    std::lock_guard<std::mutex> lk(P->mu);
+    if (P->n_running || !P->pending[0].empty() || !P->pending[1].empty())
+        return fail(TRI_EINVAL, "ivf_destroy while queries are queued or running");
+    int rc = reap(P, true, nullptr);
+    if (rc) return rc;
+    HIP_TRY(hipStreamSynchronize(P->stream));
+    // finished, unpolled tickets of this index stay valid: their results are already on the host
+    P->indexes[ix->id] = nullptr;
+    P->attached_row_bytes = 128;
+    for (tri_index *o : P->indexes)
+        if (o) P->attached_row_bytes = std::max(P->attached_row_bytes, o->row_bytes);
+    if (ix->list_base + ix->p.nlist == P->total_lists) P->total_lists = ix->list_base;   // last attached: give its list range back
+    delete ix;
+    return TRI_OK;
+}
+
+// ================================================================================== search
+extern "C" int search_submit_batch(tri_pool *P, const tri_query *q, uint32_t n, tri_ticket *out, uint32_t *n_done)
+{
+    if (n_done) *n_done = 0;
+    if (!P || (!q && n) || (!out && n)) return fail(TRI_EINVAL, "NULL argument");
+    std::lock_guard<std::mutex> lk(P->mu);
+    for (uint32_t i = 0; i < n; ++i) {
+        int rc = validate_query(P, &q[i]);
+        if (rc) return rc;          // nothing of this call has been queued yet only if i == 0; report progress
+    }
+    for (uint32_t i = 0; i < n; ++i) {
+        if (P->free_tickets.empty()) {
+            return fail(TRI_EAGAIN, "max_outstanding=%u tickets alive", P->cfg.max_outstanding);
+        }
+        enqueue_locked(P, &q[i], &out[i]);
+        if (n_done) *n_done = i + 1;
+    }
+    return TRI_OK;
+}
+
+extern "C" int search_submit(tri_pool *P, const tri_query *q, tri_ticket *out)
+{
+    if (!q || !out) return fail(TRI_EINVAL, "NULL argument");
+    return search_submit_batch(P, q, 1, out, nullptr);
+}
+
+extern "C" int search_step(tri_pool *P, tri_step_stats *st)
+{
+    if (!P) return fail(TRI_EINVAL, "pool is NULL");
+    std::lock_guard<std::mutex> lk(P->mu);
+    HIP_TRY(hipSetDevice(P->device));
+    tri_step_stats stats{};
+    int rc = reap(P, false, &stats.finished);
+    if (rc) return rc;
+    StepRec &R = P->ring[P->step_seq % RING];
+    if (R.in_use) {                       // RING steps in flight: wait for the oldest
+        HIP_TRY(hipEventSynchronize(R.done));
+        rc = reap(P, false, &stats.finished);
+        if (rc) return rc;
+    }
+    const tri_pool_cfg &cfg = P->cfg;
+    const uint32_t S = cfg.slots;
+    TriNewDesc *desc_h = (TriNewDesc *)R.up_host;
+
+    // ---- admit: high class first, FIFO inside a class
+    P->newq.clear();
+    for (int klass = 0; klass < 2; ++klass) {
+        std::deque<uint32_t> &Q = P->pending[klass];
+        while (!Q.empty() && !P->free_slots.empty()) {
+            const uint32_t ti = Q.front();
+            Q.pop_front();
+            const uint32_t slot = P->free_slots.back();
+            P->free_slots.pop_back();
+            Ticket &t = P->tickets[ti];
+            t.state = T_RUNNING;
+            t.slot = slot;
+            SlotH &sl = P->slots[slot];
+            sl = SlotH{true, ti, t.nprobe, 0u, t.klass, P->admit_seq++, t.index};
+            ++P->n_running;
+            P->newq.push_back(ti);
+        }
+    }
+    const uint32_t n_new = (uint32_t)P->newq.size();
+    // group the admitted queries by index (stable) so each index's rows are contiguous
+    std::stable_sort(P->newq.begin(), P->newq.end(), [&](uint32_t a, uint32_t b) {
+        return P->tickets[a].index->id < P->tickets[b].index->id;
+    });
+    const size_t desc_bytes = round_up_sz((size_t)n_new * sizeof(TriNewDesc), 256);
+
+    // ---- plan: every running slot, higher class first, then admission order
+    P->order.clear();
+    for (uint32_t s = 0; s < S; ++s)
+        if (P->slots[s].active) P->order.push_back(s);
+    std::sort(P->order.begin(), P->order.end(), [&](uint32_t a, uint32_t b) {
+        const SlotH &x = P->slots[a], &y = P->slots[b];
+        if (x.klass != y.klass) return x.klass < y.klass;
+        return x.admit_seq < y.admit_seq;
+    });
+    TriPlanEntry *plan_h = (TriPlanEntry *)(R.up_host + desc_bytes);
+    uint32_t n_plan = 0, n_items = 0, n_retire = 0;
+    uint64_t score_used = 0;
+    R.retire.clear();
+    for (uint32_t s : P->order) {
+        if (n_items >= cfg.items_per_step) break;
+        SlotH &sl = P->slots[s];
+        const uint32_t remaining = sl.nprobe - sl.cursor;
+        uint32_t take = cfg.lists_per_query_step ? std::min(cfg.lists_per_query_step, remaining) : remaining;
+        take = std::min(take, cfg.items_per_step - n_items);
+        const uint64_t per_item = round_up(sl.index->max_list_len, TRI_VB);
+        if (per_item) take = (uint32_t)std::min<uint64_t>(take, (P->score_capacity - score_used) / per_item);
+        if (take == 0) continue;
+        TriPlanEntry &e = plan_h[n_plan++];
+        e.slot = s; e.cursor = sl.cursor; e.take = take; e.item_base = n_items; e.pad_ = 0;
+        e.retire_idx = sl.cursor + take == sl.nprobe ? (int32_t)n_retire++ : -1;
+        if (e.retire_idx >= 0) R.retire.push_back(sl.ticket);
+        n_items += take;
+        score_used += (uint64_t)take * per_item;
+    }
+    stats.step = P->step_seq;
+    stats.admitted = n_new;
+    stats.retired = n_retire;
+    stats.running = P->n_running;
+    stats.items = n_items;
+    stats.capacity = cfg.items_per_step;
+    stats.pending_high = (uint32_t)P->pending[0].size();
+    stats.pending_low = (uint32_t)P->pending[1].size();
+    if (n_new == 0 && n_plan == 0) {
+        if (st) *st = stats;
+        return TRI_OK;
+    }
+
+    // ---- upload block: [descs][plan][rows]
+    const size_t plan_bytes = round_up_sz((size_t)n_plan * sizeof(TriPlanEntry), 256);
+    uint8_t *rows_h = R.up_host + desc_bytes + plan_bytes;
+    uint32_t row_off = 0;
+    for (uint32_t i = 0; i < n_new; ++i) {
+        const Ticket &t = P->tickets[P->newq[i]];
+        desc_h[i] = TriNewDesc{t.slot, t.index->id, t.metric, t.k, t.nprobe, row_off};
+        memcpy(rows_h + row_off, &P->qstore[(size_t)P->newq[i] * P->max_row_bytes], t.index->row_bytes);
+        row_off += t.index->row_bytes;
+    }
+    const size_t up_bytes = desc_bytes + plan_bytes + row_off;
+    hipStream_t s = P->stream;
+    const bool prof = (cfg.flags & TRI_FLAG_PROFILE) != 0;
+    HIP_TRY(hipMemcpyAsync(P->ws.upload, R.up_host, up_bytes, hipMemcpyHostToDevice, s));
+    const TriNewDesc *desc_d = (const TriNewDesc *)P->ws.upload;
+    const TriPlanEntry *plan_d = (const TriPlanEntry *)(P->ws.upload + desc_bytes);
+    const uint8_t *rows_d = P->ws.upload + desc_bytes + plan_bytes;
+
+    if (prof) HIP_TRY(hipEventRecord(R.ev[0], s));
+    HIP_TRY(tri_launch_admit(P->ctx, P->ws, desc_d, rows_d, n_new));
+    if (prof) HIP_TRY(hipEventRecord(R.ev[1], s));
+    // ---- coarse ranking of the admitted queries, index by index
+    for (uint32_t a = 0; a < n_new;) {
+        tri_index *ix = P->tickets[P->newq[a]].index;
+        uint32_t b = a;
+        while (b < n_new && P->tickets[P->newq[b]].index == ix) ++b;
+        const uint32_t ldc = round_up(ix->p.nlist, 32);
+        for (uint32_t c = a; c < b; c += P->coarse_rows) {
+            const uint32_t m = std::min(P->coarse_rows, b - c);
+            HIP_TRY(tri_launch_coarse_gemm(s, (int)ix->p.dtype, rows_d + desc_h[c].row_off, ix->row_bytes, m,
+                                           ix->dev.centroids, ix->dev.cnorm, ix->p.nlist, ix->row_bytes,
+                                           &desc_d[c].metric, sizeof(TriNewDesc) / 4, 0u, P->ws.coarse_scores, ldc));
+            HIP_TRY(tri_launch_coarse_select(P->ctx, P->ws, desc_d, c, m, ix->p.nlist, ldc));
+        }
+        a = b;
+    }
+    if (prof) HIP_TRY(hipEventRecord(R.ev[2], s));
+    HIP_TRY(tri_launch_pack(P->ctx, P->ws, plan_d, n_plan, n_items, P->total_lists));
+    if (prof) HIP_TRY(hipEventRecord(R.ev[3], s));
+    if (n_items) HIP_TRY(tri_launch_scan(P->ctx, P->ws, P->attached_row_bytes));
+    if (prof) HIP_TRY(hipEventRecord(R.ev[4], s));
+    HIP_TRY(tri_launch_merge(P->ctx, P->ws, plan_d, n_plan, (cfg.flags & TRI_FLAG_KEEP_PROBES) != 0));
+    if (n_retire) {
+        HIP_TRY(hipMemcpyAsync(R.down_host, P->ws.res_block, (size_t)n_retire * (1 + 2 * (size_t)cfg.kmax) * 4,
+                               hipMemcpyDeviceToHost, s));
+        if (cfg.flags & TRI_FLAG_KEEP_PROBES)
+            HIP_TRY(hipMemcpyAsync(R.down_host + P->down_probe_off, P->ws.res_probes,
+                                   (size_t)n_retire * cfg.nprobe_max * 4, hipMemcpyDeviceToHost, s));
+    }
+    if (prof) {
+        HIP_TRY(hipMemcpyAsync(R.down_host + P->down_step_off, P->ws.step_dev, sizeof(TriStepDev), hipMemcpyDeviceToHost, s));
+        HIP_TRY(hipEventRecord(R.ev[5], s));
+    }
+    HIP_TRY(hipEventRecord(R.done, s));
+    R.in_use = true;
+    R.profiled = prof;
+    R.seq = P->step_seq;
+    R.n_items = n_items;
+    R.had_scan = n_items != 0;
+
+    // ---- host mirror: advance cursors, retire, recycle slots
+    for (uint32_t i = 0; i < n_plan; ++i) {
+        const TriPlanEntry &e = plan_h[i];
+        SlotH &sl = P->slots[e.slot];
+        sl.cursor += e.take;
+        if (e.retire_idx >= 0) {
+            Ticket &t = P->tickets[sl.ticket];
+            t.state = T_RETIRING;
+            t.step_seq = P->step_seq;
+            t.retire_idx = (uint32_t)e.retire_idx;
+            sl.active = false;
+            P->free_slots.push_back(e.slot);
+            --P->n_running;
+        }
+    }
+    ++P->step_seq;
+    if (st) *st = stats;
+    return TRI_OK;
+}
+
+namespace {
+// search_poll without the lock and without the reap; returns TRI_OK / TRI_EAGAIN / TRI_ENOENT / TRI_EINVAL
+int poll_locked(tri_pool *P, tri_ticket tk, uint32_t *n_out, int64_t *ids, float *dist, uint32_t room)
+{
+    uint32_t ti;
+    if (!ticket_lookup(P, tk, &ti)) return fail(TRI_ENOENT, "unknown ticket");
+    Ticket &t = P->tickets[ti];
+    if (t.cancelled) return fail(TRI_ENOENT, "ticket was cancelled");
+    if (t.state != T_DONE) return TRI_EAGAIN;
+    if (!ids || !dist) return fail(TRI_EINVAL, "ids / dist is NULL");
+    if (room < t.k) return fail(TRI_EINVAL, "row of %u entries is too short for k=%u", room, t.k);
+    const uint32_t kmax = P->cfg.kmax;
+    for (uint32_t i = 0; i < t.n_out; ++i) {
+        ids[i] = (int64_t)P->res_ids[(size_t)ti * kmax + i];
+        dist[i] = P->res_score[(size_t)ti * kmax + i];
+    }
+    const float pad = t.metric == TRI_L2 ? __builtin_inff() : -__builtin_inff();
+    for (uint32_t i = t.n_out; i < t.k; ++i) { ids[i] = -1; dist[i] = pad; }
+    if (n_out) *n_out = t.n_out;
+    t.state = T_FREE;
+    ++t.gen;
+    P->free_tickets.push_back(ti);
+    return TRI_OK;
+}
+}  // namespace
+
+extern "C" int search_poll(tri_pool *P, tri_ticket tk, uint32_t *n_out, int64_t *ids, float *dist)
+{
+    if (!P) return fail(TRI_EINVAL, "pool is NULL");
+    std::lock_guard<std::mutex> lk(P->mu);
+    HIP_TRY(hipSetDevice(P->device));
+    int rc = reap(P, false, nullptr);
+    if (rc) return rc;
+    return poll_locked(P, tk, n_out, ids, dist, 0xFFFFFFFFu);
+}
+
+extern "C" int search_poll_batch(tri_pool *P, const tri_ticket *tk, uint32_t n, uint32_t stride, uint32_t *n_out,
+                                 int64_t *ids, float *dist, int *status)
+{
+    if (!P || (n && (!tk || !ids || !dist || !status || !n_out))) return fail(TRI_EINVAL, "NULL argument");
+    std::lock_guard<std::mutex> lk(P->mu);
+    HIP_TRY(hipSetDevice(P->device));
+    int rc = reap(P, false, nullptr);
+    if (rc) return rc;
+    int delivered = 0;
+    for (uint32_t i = 0; i < n; ++i) {
+        status[i] = poll_locked(P, tk[i], &n_out[i], ids + (size_t)i * stride, dist + (size_t)i * stride, stride);
+        delivered += status[i] == TRI_OK;
+    }
+    return delivered;
+}
+
+extern "C" int search_probes(tri_pool *P, tri_ticket tk, uint32_t *lists, uint32_t *n_out)
+{
+    if (!P || !lists) return fail(TRI_EINVAL, "NULL argument");
+    std::lock_guard<std::mutex> lk(P->mu);
+    if (!(P->cfg.flags & TRI_FLAG_KEEP_PROBES)) return fail(TRI_EINVAL, "pool was created without TRI_FLAG_KEEP_PROBES");
+    uint32_t ti;
+    if (!ticket_lookup(P, tk, &ti)) return fail(TRI_ENOENT, "unknown ticket");
+    Ticket &t = P->tickets[ti];
+    if (t.cancelled) return fail(TRI_ENOENT, "ticket was cancelled");
+    if (t.state == T_RETIRING) {
+        HIP_TRY(hipSetDevice(P->device));
+        int rc = reap(P, false, nullptr);
+        if (rc) return rc;
+    }
+    if (t.state != T_DONE) return TRI_EAGAIN;
+    memcpy(lists, &P->res_probe[(size_t)ti * P->cfg.nprobe_max], (size_t)t.nprobe * 4);
+    if (n_out) *n_out = t.nprobe;
+    return TRI_OK;
+}
+
+extern "C" int search_cancel(tri_pool *P, tri_ticket tk)
+{
+    if (!P) return fail(TRI_EINVAL, "pool is NULL");
+    std::lock_guard<std::mutex> lk(P->mu);
+    uint32_t ti;
+    if (!ticket_lookup(P, tk, &ti)) return fail(TRI_ENOENT, "unknown ticket");
+    Ticket &t = P->tickets[ti];
+    if (t.cancelled) return fail(TRI_ENOENT, "ticket was cancelled");
+    if (t.state == T_PENDING) {
+        std::deque<uint32_t> &Q = P->pending[t.klass];
+        Q.erase(std::find(Q.begin(), Q.end(), ti));
+        t.state = T_FREE;
+        ++t.gen;
+        P->free_tickets.push_back(ti);
+    } else if (t.state == T_DONE) {
+        t.state = T_FREE;
+        ++t.gen;
+        P->free_tickets.push_back(ti);
+    } else {
+        t.cancelled = true;       // running / retiring: freed when its step is reaped
+    }
+    return TRI_OK;
+}
+
+extern "C" int search_sync(tri_pool *P)
+{
+    if (!P) return fail(TRI_EINVAL, "pool is NULL");
+    std::lock_guard<std::mutex> lk(P->mu);
+    HIP_TRY(hipSetDevice(P->device));
+    return reap(P, true, nullptr);
+}
+
+extern "C" int tri_pool_kernel_times(tri_pool *P, tri_kernel_times *out, int reset)
+{
+    if (!P || !out) return fail(TRI_EINVAL, "NULL argument");
+    std::lock_guard<std::mutex> lk(P->mu);
+    *out = P->times;
+    if (reset) P->times = tri_kernel_times{};
+    return TRI_OK;
+}
+
+extern "C" const char *tri_last_error(void) { return g_err.c_str(); }
+extern "C" const char *tri_version(void) { return "trinity-ivf-mi355x 0.1 (gfx950)"; }

@@ -1,0 +1,150 @@
+// Shared declarations of the HIP library's translation units (device-side layouts, launchers).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <stddef.h>
+
+#define TRI_QT 32            // queries per scan tile (columns of one MFMA output block)
+#define TRI_VB 32            // vectors per scan block (rows of one MFMA output block)
+#define TRI_SEL_THREADS 256  // threads of a selection workgroup
+#define TRI_SCAN_THREADS 256 // threads of a scan workgroup (4 wavefronts)
+#define TRI_KMAX_POW2 1024   // largest k (and nprobe) a selection can return
+
+// One attached index as the kernels see it.  All pointers are device pointers.
+struct TriIndexDev {
+    const void *vecs;        // list-major vectors, row pitch row_bytes, 256-B aligned
+    const float *vnorm;      // |x|^2 per stored vector (list-major order), fp32
+    const uint32_t *ids;     // base-row number per stored vector (list-major order)
+    const uint32_t *list_off;// [nlist+1] first stored position of each list
+    const void *centroids;   // [nlist] rows of pitch row_bytes, index dtype
+    const float *cnorm;      // |c|^2 per centroid, fp32
+    uint32_t dim, dpad, nlist, dtype;
+    uint32_t row_bytes;      // dpad * element size, multiple of 128
+    uint32_t list_base;      // number of this index's list 0 in the pool-wide list numbering
+    uint32_t max_list_len;
+    uint32_t pad_;
+    uint64_t n;
+};
+
+// Static description of the request in a slot (written at admission).
+struct TriSlotMeta {
+    uint32_t index;   // which attached index
+    uint32_t metric;  // TRI_L2 / TRI_IP
+    uint32_t k;
+    uint32_t nprobe;
+};
+
+// One admitted query in the step's upload block.
+struct TriNewDesc {
+    uint32_t slot, index, metric, k, nprobe;
+    uint32_t row_off;   // byte offset of its padded row inside the uploaded row area
+};
+
+// One running slot's share of this step.
+struct TriPlanEntry {
+    uint32_t slot;
+    uint32_t cursor;     // probe-list rank of the first list scanned in this step
+    uint32_t take;       // lists scanned in this step
+    uint32_t item_base;  // first work item of this slot in the unsorted item array
+    int32_t retire_idx;  // >= 0: the slot finishes in this step, result goes to this record
+    uint32_t pad_;
+};
+
+// One scan tile: up to TRI_QT queries against one whole inverted list.
+struct TriTile {
+    uint32_t glist;      // pool-wide list number
+    uint32_t item_pos;   // first of the tile's queries in the list-sorted item array
+    uint32_t nq;         // 1..TRI_QT real queries
+    uint32_t pad_;
+    uint64_t score_off;  // element offset of query 0's score segment; query j at + j*npad
+};
+
+// Small per-step numbers the device produces for the host (copied back with the results).
+struct TriStepDev {
+    uint32_t n_tiles;
+    uint32_t n_lists_touched;
+    uint64_t total_scores;
+    uint64_t tile_vec_bytes;    // sum over tiles of list_len * row_bytes
+    uint64_t unique_vec_bytes;  // sum over touched lists of list_len * row_bytes
+};
+
+// Device workspace of a pool, carved once at creation.
+struct TriDevWs {
+    // persistent per-slot state
+    uint8_t *slot_query;      // [S][slot_row_bytes]
+    TriSlotMeta *slot_meta;   // [S]
+    float *slot_qnorm;        // [S]
+    uint32_t *probe;          // [S][nprobe_max]
+    float *topk_score;        // [S][kmax]
+    uint32_t *topk_id;        // [S][kmax]
+    uint32_t *topk_count;     // [S]
+    // attached indexes and the pool-wide list table
+    TriIndexDev *indexes;     // [max_indexes]
+    uint32_t *glist_len;      // [max_total_lists]
+    uint32_t *glist_voff;     // [max_total_lists] first stored position inside its index
+    uint32_t *glist_index;    // [max_total_lists]
+    // per-step upload block (device copy)
+    uint8_t *upload;          // upload_bytes
+    // coarse ranking
+    float *coarse_scores;     // [coarse_rows][max_nlist]
+    // packing
+    uint32_t *item_glist;     // [W]
+    uint32_t *item_slot;      // [W]
+    uint32_t *item_rank;      // [W]
+    uint64_t *item_score_off; // [W]
+    uint32_t *sorted_slot;    // [W]
+    uint32_t *hist;           // [max_total_lists+1]
+    uint32_t *list_start;     // [max_total_lists+1]
+    uint32_t *tile_base;      // [max_total_lists+1]
+    uint64_t *score_base;     // [max_total_lists+1]
+    TriTile *tiles;           // [W]
+    uint32_t *tile_counter;   // [1] work-queue head of the scan kernel
+    TriStepDev *step_dev;     // [1]
+    float *scores;            // [score_capacity]
+    // results of retiring slots, compact, per step
+    uint32_t *res_block;      // [S][1 + 2*kmax]  n, ids[kmax], score bits[kmax]
+    uint32_t *res_probes;     // [S][nprobe_max]
+};
+
+struct TriLaunchCtx {
+    hipStream_t stream;
+    uint32_t S, W, kmax, nprobe_max, max_total_lists, slot_row_bytes, n_cu;
+};
+
+// ---- launchers (each returns hipGetLastError() of its launches) -----------------------------
+hipError_t tri_launch_fill_u32(hipStream_t s, uint32_t *p, uint32_t v, size_t n);
+hipError_t tri_launch_admit(const TriLaunchCtx &c, const TriDevWs &ws, const TriNewDesc *desc_dev,
+                            const uint8_t *rows_dev, uint32_t n_new);
+// scores[m][ldc] for m rows (pitch a_pitch_bytes) against n rows of b (pitch row_bytes); the metric
+// is per row (row_metric[m * metric_stride_u32]) or, with row_metric == NULL, fixed_metric.
+hipError_t tri_launch_coarse_gemm(hipStream_t s, int dtype, const void *a_rows, uint32_t a_pitch_bytes,
+                                  uint32_t m, const void *b_rows, const float *b_norm, uint32_t n,
+                                  uint32_t row_bytes, const uint32_t *row_metric, uint32_t metric_stride_u32,
+                                  uint32_t fixed_metric, float *scores, uint32_t ldc);
+hipError_t tri_launch_coarse_select(const TriLaunchCtx &c, const TriDevWs &ws, const TriNewDesc *desc_dev,
+                                    uint32_t first_new, uint32_t m, uint32_t nlist, uint32_t ldc);
+hipError_t tri_launch_pack(const TriLaunchCtx &c, const TriDevWs &ws, const TriPlanEntry *plan_dev,
+                           uint32_t n_plan, uint32_t n_items, uint32_t total_lists);
+hipError_t tri_launch_scan(const TriLaunchCtx &c, const TriDevWs &ws, uint32_t max_row_bytes);
+hipError_t tri_launch_merge(const TriLaunchCtx &c, const TriDevWs &ws, const TriPlanEntry *plan_dev,
+                            uint32_t n_plan, bool keep_probes);
+hipError_t tri_scan_configure(uint32_t max_row_bytes);   // raises the scan kernel's dynamic-LDS limit
+
+// ---- index construction helpers ------------------------------------------------------------
+hipError_t tri_build_pad_rows(hipStream_t s, int dtype, const void *src, uint32_t dim, uint64_t src_pitch_elems,
+                              const uint32_t *row_sel, uint64_t row_mul, uint64_t row_add, uint64_t row_mod,
+                              uint64_t nrows, void *dst, uint32_t dpad);
+hipError_t tri_build_widen_rows(hipStream_t s, int dtype, const void *src, uint64_t n_elems, float *dst);
+hipError_t tri_build_convert_centroids(hipStream_t s, int dtype, const float *cent_f32, uint32_t nlist,
+                                       uint32_t dpad, void *dst);
+hipError_t tri_build_row_norms(hipStream_t s, int dtype, const void *rows, uint32_t dpad, uint64_t nrows,
+                               float *out);
+hipError_t tri_build_argbest(hipStream_t s, const float *scores, uint32_t ldc, uint32_t nrows, uint32_t ncols,
+                             int metric, uint32_t *out);
+hipError_t tri_build_partition(hipStream_t s, const uint32_t *assign, uint64_t nrows, uint32_t nlist,
+                               uint32_t *block_hist /*[nblocks][nlist]*/, uint32_t nblocks,
+                               uint32_t *list_len_tmp /*[nlist]*/, uint32_t *list_off /*[nlist+1]*/,
+                               uint32_t *perm /*[nrows]*/);
+hipError_t tri_build_cluster_means(hipStream_t s, int dtype, const void *rows, uint32_t dpad,
+                                   const uint32_t *list_off, const uint32_t *perm, uint32_t nlist, int normalise,
+                                   float *cent_f32 /*[nlist][dpad] in/out*/);
