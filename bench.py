@@ -1,0 +1,224 @@
+#!/usr/bin/env python3
+"""Benchmark of the batched IVF search path on one MI355X.
+
+A "step" is one pass of the whole hot path (admit -> coarse assignment -> pack -> list scan ->
+top-k merge -> retire) over one batch of synthetic queries whose vectors are already resident in
+HBM.  Default workload: configuration 4 (10M x 768 fp16, inner product, nlist 16384, batches of
+4096 queries, nprobe 64, k 100).  Prints ONE JSON line.
+
+  python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload config4|config2|config1]
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0   # MI355X published HBM3E bandwidth
+
+
+def log(msg):
+    print(f"[bench] {msg}", file=sys.stderr, flush=True)
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="config4", choices=["config4", "config2", "config1"])
+    ap.add_argument("--cpu-sample", type=int, default=-1, help="queries timed on the CPU oracle (0 = skip)")
+    ap.add_argument("--recall-sample", type=int, default=64)
+    ap.add_argument("--copy-calibration-mib", type=int, default=0,
+                    help="run one plain device copy of this many MiB before timing (a kernel of known traffic, "
+                         "to scale profiler byte counters)")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU (the path does not shard in this round); run with --gpus 1",
+              file=sys.stderr)
+        sys.exit(2)
+
+    lib_path = os.path.join(ROOT, "paper_2512_02281_amd", "libtrinity_ivf.so")
+    if not os.path.exists(lib_path):
+        from paper_2512_02281_amd.build import build_library  # the only case in which bench builds
+        build_library()
+    import torch
+    import paper_2512_02281_amd as tri
+    import workloads
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU", file=sys.stderr)
+        sys.exit(3)
+    number = int(args.workload[-1])
+    cfg = workloads.CONFIGS[number]
+    t_start = time.time()
+    log(f"workload {cfg.name}: generating {cfg.n_base} x {cfg.dim}")
+    if number == 1:
+        base_np, queries_np, rows = workloads.make_config01(cfg)
+        base_t = torch.from_numpy(base_np).cuda()
+        queries_t = torch.from_numpy(queries_np).cuda()
+        dtype, metric, tdtype = tri.TRI_F32, tri.TRI_L2, "f32"
+        k = np.full(cfg.n_queries, cfg.k, dtype=np.uint32)
+        nprobe = np.full(cfg.n_queries, cfg.nprobe, dtype=np.uint32)
+    else:
+        base_t, queries_t, rows = workloads.make_config_f16(cfg, device="cuda")
+        dtype, metric, tdtype = tri.TRI_F16, tri.TRI_IP, "f16"
+        if number == 2:
+            k, nprobe = workloads.hetero_params(cfg.n_queries, cfg.seed_params)
+        else:
+            k = np.full(cfg.n_queries, cfg.k, dtype=np.uint32)
+            nprobe = np.full(cfg.n_queries, cfg.nprobe, dtype=np.uint32)
+    torch.cuda.synchronize()
+    Q = cfg.n_queries
+    kmax = int(k.max())
+    items = int(nprobe.sum())
+
+    pool = tri.Pool(slots=Q, items_per_step=items, lists_per_query_step=0, kmax=max(kmax, 16),
+                    nprobe_max=int(nprobe.max()), max_indexes=1, max_total_lists=cfg.nlist, max_nlist=cfg.nlist,
+                    max_dim=cfg.dim, max_outstanding=Q * 8, coarse_rows=0, flags=tri.TRI_FLAG_PROFILE,
+                    score_capacity=(1 << 30))
+    log("building the index (untimed)")
+    t_b = time.time()
+    init = base_t[torch.from_numpy(rows).cuda()].float().cpu().numpy()
+    index = pool.build_index(base_t, cfg.dim, cfg.nlist, dtype, metric, cfg.train_iters, centroids=init)
+    info = tri.ivf_info(index)
+    log(f"index built in {time.time() - t_b:.1f}s; longest list {info['max_list_len']}")
+    metric_arr = np.full(Q, metric, dtype=np.uint32)
+    es = 2 if dtype == tri.TRI_F16 else 4
+    qptr, pitch = queries_t.data_ptr(), cfg.dim * es
+
+    def one_batch():
+        tickets, rc = tri.search_submit_batch_dev(pool.handle, index, qptr, pitch, Q, k, nprobe, metric_arr)
+        assert rc == tri.TRI_OK and tickets.shape[0] == Q
+        launches = 0
+        while True:
+            st = tri.search_step(pool.handle)
+            launches += st.items > 0
+            if st.running == st.retired and st.pending_low == 0 and st.pending_high == 0:
+                break                         # every running query retires in the step just enqueued
+            assert launches < 10000
+        return tickets, launches
+
+    def drain(tickets):
+        ids, dist, n_out, status = tri.search_poll_batch(pool.handle, tickets, kmax)
+        assert np.all(status == tri.TRI_OK), "a query of a finished batch was not pollable"
+        return ids, dist, n_out
+
+    if args.copy_calibration_mib:
+        src = torch.ones(args.copy_calibration_mib << 18, dtype=torch.float32, device="cuda")
+        dst = torch.empty_like(src)
+        dst.copy_(src)                      # reads and writes copy_calibration_mib MiB each
+        torch.cuda.synchronize()
+        del src, dst
+    log(f"warmup {args.warmup}")
+    last = None
+    for _ in range(max(args.warmup, 1)):
+        tickets, launches_per_batch = one_batch()
+        tri.search_sync(pool.handle)
+        last = drain(tickets)
+    tri.tri_pool_kernel_times(pool.handle, reset=True)
+
+    log(f"timing {args.steps} steps")
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    inflight = []
+    for i in range(args.steps):
+        tickets, _ = one_batch()
+        inflight.append(tickets)
+        if len(inflight) > 2:                 # results of two batches ago are pollable by now or very soon
+            t_old = inflight.pop(0)
+            ids, dist, n_out, status = tri.search_poll_batch(pool.handle, t_old, kmax)
+            pending = t_old[status == tri.TRI_EAGAIN]
+            if pending.size:
+                inflight.insert(0, pending)
+    tri.search_sync(pool.handle)
+    for t_old in inflight:
+        drain(t_old)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    total_s = t1 - t0
+    ms_per_step = total_s * 1e3 / args.steps
+    qps = Q * args.steps / total_s
+    kt = tri.tri_pool_kernel_times(pool.handle)
+    scan_ms = kt.scan_ms / max(kt.scan_launches, 1)
+    unique_b = kt.scan_unique_bytes / max(kt.scan_launches, 1)
+    tile_b = kt.scan_vector_bytes / max(kt.scan_launches, 1)
+    row_bytes = -(-cfg.dim * es // 128) * 128
+    achieved = unique_b / (scan_ms * 1e-3) / 1e9 if scan_ms > 0 else 0.0
+    log(f"{ms_per_step:.3f} ms/step, {qps:.0f} q/s; scan {scan_ms:.3f} ms/launch, unique {unique_b / 1e9:.2f} GB "
+        f"-> {achieved:.0f} GB/s; stages ms/step: admit {kt.admit_ms / kt.steps:.3f} coarse {kt.coarse_ms / kt.steps:.3f} "
+        f"pack {kt.pack_ms / kt.steps:.3f} scan {kt.scan_ms / kt.steps:.3f} select {kt.select_ms / kt.steps:.3f}")
+
+    # ---- recall of the returned lists against exact search (torch matmul on the GPU, harness only)
+    recall = None
+    if args.recall_sample:
+        ids, dist, n_out = last
+        rs = np.random.default_rng(77).choice(Q, size=min(args.recall_sample, Q), replace=False)
+        qs = queries_t[torch.from_numpy(rs).cuda()]
+        hits = tot = 0
+        for j, qi in enumerate(rs):
+            kk = int(k[qi])
+            if metric == tri.TRI_IP:
+                sc = (base_t @ qs[j]).float()
+                top = torch.topk(sc, kk).indices
+            else:
+                sc = ((base_t - qs[j]) ** 2).sum(dim=1)
+                top = torch.topk(sc, kk, largest=False).indices
+            hits += len(set(top.cpu().numpy().tolist()) & set(ids[qi, :kk].tolist()))
+            tot += kk
+        recall = hits / tot
+        log(f"recall@k on {rs.size} queries: {recall:.4f}")
+
+    # ---- the CPU oracle on a bounded sample of the same batch, same box
+    cpu = None
+    n_cpu = args.cpu_sample if args.cpu_sample >= 0 else {4: 1024, 2: 1024, 1: 1024}[number]
+    if n_cpu:
+        import oracle
+        log("exporting the index and copying the base to the host for the CPU oracle")
+        cent, off, lids = tri.ivf_export(index)
+        base_host = base_t.cpu().numpy()
+        oidx = oracle.Index(base_host, cent, off, lids)
+        sel = np.arange(0, Q, max(1, Q // n_cpu))[:n_cpu]
+        qh = queries_t.cpu().numpy()[sel]
+        tc0 = time.perf_counter()
+        out = oracle.search_batch(oidx, qh, k[sel], nprobe[sel], metric_arr[sel])
+        tc = time.perf_counter() - tc0
+        cpu = {"value": round(sel.size / tc, 3), "unit": "queries/s", "cores": out["threads"], "kind": "oracle",
+               "sample": f"{sel.size} queries of the same batch (every {max(1, Q // n_cpu)}-th), {tc:.1f} s of wall time"}
+        log(f"cpu oracle: {cpu}")
+
+    result = {
+        "metric": "queries/sec at recall@k>=0.9 (1 GPU) + list-scan HBM GB/s as % of peak",
+        "value": round(qps, 1), "unit": "queries/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": tdtype, "data": "synthetic",
+        "config": {"workload": f"configs[{number}] {cfg.name}: {cfg.n_base} x {cfg.dim} {tdtype}, nlist {cfg.nlist}, "
+                               f"{Q} queries/step, nprobe {int(nprobe.max()) if number != 2 else 'U{8..128}'}, "
+                               f"k {kmax if number != 2 else 'U{1,10,100}'}",
+                   "queries_per_step": Q, "items_per_step": items, "launches_per_step": launches_per_batch,
+                   "recall_at_k": None if recall is None else round(recall, 4),
+                   "longest_list": info["max_list_len"], "query_vectors": "device-resident"},
+        "roofline": {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": None,
+                     "kernel": "scan_kernel", "avg_launch_ms": round(scan_ms, 4),
+                     "algorithmic_bytes_per_launch": int(unique_b), "tile_bytes_per_launch": int(tile_b),
+                     "items_per_launch": int(kt.scan_items / max(kt.scan_launches, 1)), "row_bytes": row_bytes},
+        "stages_ms_per_step": {"admit": round(kt.admit_ms / kt.steps, 4), "coarse": round(kt.coarse_ms / kt.steps, 4),
+                               "pack": round(kt.pack_ms / kt.steps, 4), "scan": round(kt.scan_ms / kt.steps, 4),
+                               "select": round(kt.select_ms / kt.steps, 4)},
+        "cpu_baseline": cpu,
+        "wall_s_total": round(time.time() - t_start, 1),
+    }
+    pool.close()
+    print(json.dumps(result), flush=True)
+
+
+if __name__ == "__main__":
+    main()

@@ -154,6 +154,16 @@ int search_submit(tri_pool *pool, const tri_query *q /*[host]*/, tri_ticket *out
 int search_submit_batch(tri_pool *pool, const tri_query *q /*[host] n*/, uint32_t n,
                         tri_ticket *out /*[host] n*/, uint32_t *n_done /*[host] out or NULL*/);
 
+/* Queue n queries against ONE index whose vectors already live in device memory (for instance
+ * the output of an embedding model on the same GPU).  vecs [device]: n rows of dim elements of the
+ * index's dtype, row pitch pitch_bytes (a multiple of the element size); the rows are read by the
+ * step that admits each query, so they must stay valid and unchanged until the ticket is finished.
+ * k / nprobe / metric / klass: [host] arrays of n.  Same return values as search_submit_batch. */
+int search_submit_batch_dev(tri_pool *pool, const tri_index *index, const void *vecs /*[device]*/,
+                            uint64_t pitch_bytes, uint32_t n, const uint32_t *k, const uint32_t *nprobe,
+                            const uint32_t *metric, const uint32_t *klass, tri_ticket *out /*[host] n*/,
+                            uint32_t *n_done /*[host] out or NULL*/);
+
 typedef struct {
     uint64_t step;        /* sequence number of this step                                          */
     uint32_t admitted;    /* queries moved from the queues into slots                              */

@@ -73,8 +73,8 @@ class tri_kernel_times(ctypes.Structure):
 
 
 EXPORTS = ["tri_pool_workspace_bytes", "tri_pool_create", "tri_pool_destroy", "ivf_build_bytes", "ivf_build",
-           "ivf_export", "ivf_info", "ivf_destroy", "search_submit", "search_submit_batch", "search_step",
-           "search_poll", "search_poll_batch", "search_probes", "search_cancel", "search_sync",
+           "ivf_export", "ivf_info", "ivf_destroy", "search_submit", "search_submit_batch", "search_submit_batch_dev",
+           "search_step", "search_poll", "search_poll_batch", "search_probes", "search_cancel", "search_sync",
            "tri_pool_kernel_times", "tri_last_error", "tri_version"]
 
 
@@ -82,6 +82,9 @@ def _load():
     if not os.path.exists(LIB_PATH):
         raise ImportError(f"{LIB_PATH} is missing: build it first (python -c 'import __graft_entry__ as g; g.build()'); "
                           "this package has no fallback path")
+    # PyTorch supplies the device memory and the stream this library works on, so both must talk to the
+    # same HIP runtime instance: let torch load its runtime first, the library then binds to that one.
+    import torch  # noqa: F401
     lib = ctypes.CDLL(LIB_PATH)
     vp, u32, u64, sz = ctypes.c_void_p, ctypes.c_uint32, ctypes.c_uint64, ctypes.c_size_t
     P = ctypes.POINTER
@@ -95,6 +98,7 @@ def _load():
     lib.ivf_destroy.argtypes = [vp]
     lib.search_submit.argtypes = [vp, P(tri_query), P(u64)]
     lib.search_submit_batch.argtypes = [vp, vp, u32, vp, P(u32)]
+    lib.search_submit_batch_dev.argtypes = [vp, vp, vp, u64, u32, vp, vp, vp, vp, vp, P(u32)]
     lib.search_step.argtypes = [vp, P(tri_step_stats)]
     lib.search_poll.argtypes = [vp, u64, P(u32), vp, vp]
     lib.search_poll_batch.argtypes = [vp, vp, u32, u32, vp, vp, vp, vp]
@@ -231,6 +235,20 @@ def search_submit_batch(pool: int, queries: np.ndarray):
     return tickets[:done.value], rc
 
 
+def search_submit_batch_dev(pool: int, index: int, vecs_ptr: int, pitch_bytes: int, n: int, k, nprobe, metric,
+                            klass=TRI_CLASS_LOW):
+    """Queries whose vectors already live in device memory (vecs_ptr: device address of n rows).
+    k / nprobe / metric / klass: scalars or arrays of n.  Returns (tickets, status)."""
+    arrs = [np.ascontiguousarray(np.broadcast_to(np.asarray(a, dtype=np.uint32), (n,))) for a in (k, nprobe, metric, klass)]
+    tickets = np.zeros(n, dtype=np.uint64)
+    done = ctypes.c_uint32(0)
+    rc = _lib.search_submit_batch_dev(ctypes.c_void_p(pool), ctypes.c_void_p(index), ctypes.c_void_p(vecs_ptr),
+                                      pitch_bytes, n, _np_ptr(arrs[0]), _np_ptr(arrs[1]), _np_ptr(arrs[2]),
+                                      _np_ptr(arrs[3]), _np_ptr(tickets), ctypes.byref(done))
+    _check(rc, "search_submit_batch_dev", ok=(TRI_OK, TRI_EAGAIN))
+    return tickets[:done.value], rc
+
+
 def search_step(pool: int, stats: Optional[tri_step_stats] = None) -> tri_step_stats:
     st = stats if stats is not None else tri_step_stats()
     _check(_lib.search_step(ctypes.c_void_p(pool), ctypes.byref(st)), "search_step")
@@ -253,8 +271,8 @@ def search_poll_batch(pool: int, tickets: np.ndarray, stride: int):
     """(ids int64 [n, stride], dist fp32 [n, stride], n_out uint32 [n], status int32 [n])."""
     tickets = np.ascontiguousarray(tickets, dtype=np.uint64)
     n = tickets.shape[0]
-    ids = np.empty((n, stride), dtype=np.int64)
-    dist = np.empty((n, stride), dtype=np.float32)
+    ids = np.full((n, stride), -1, dtype=np.int64)          # entries past a query's own k stay -1 / nan
+    dist = np.full((n, stride), np.nan, dtype=np.float32)
     n_out = np.zeros(n, dtype=np.uint32)
     status = np.zeros(n, dtype=np.int32)
     rc = _lib.search_poll_batch(ctypes.c_void_p(pool), _np_ptr(tickets), n, stride, _np_ptr(n_out), _np_ptr(ids),

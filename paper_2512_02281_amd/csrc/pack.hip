@@ -20,10 +20,34 @@ hipError_t tri_launch_fill_u32(hipStream_t s, uint32_t *p, uint32_t v, size_t n)
 }
 
 // ---------------------------------------------------------------------------------------- admit
-// One workgroup per admitted query: copy its padded row into the slot, compute |q|^2 in fp32
-// (fixed order: thread-strided partial sums, then a tree), write the slot's static description.
-__global__ __launch_bounds__(256) void admit_kernel(const TriNewDesc *__restrict__ desc,
-                                                    const uint8_t *__restrict__ rows,
+// One workgroup per admitted query: bring its zero-padded row into the slot (from the uploaded row
+// area, or from the caller's device vector, which is then also written to the row area for the
+// coarse contraction), compute |q|^2 in fp32 (fixed order: thread-strided partial sums, then a
+// tree), write the slot's static description.
+template <typename T>
+__device__ __forceinline__ float admit_row(const TriNewDesc &d, uint32_t dim, uint32_t dpad, uint8_t *rows,
+                                           uint8_t *slot_row)
+{
+    T *up = (T *)(rows + d.row_off);
+    T *dst = (T *)slot_row;
+    const T *dev = (const T *)d.src_dev;
+    float part = 0.f;
+    for (uint32_t e = threadIdx.x; e < dpad; e += 256) {
+        T v;
+        if (dev) {
+            v = e < dim ? dev[e] : (T)0;
+            up[e] = v;
+        } else {
+            v = up[e];
+        }
+        dst[e] = v;
+        const float f = (float)v;
+        part += f * f;
+    }
+    return part;
+}
+
+__global__ __launch_bounds__(256) void admit_kernel(const TriNewDesc *__restrict__ desc, uint8_t *__restrict__ rows,
                                                     const TriIndexDev *__restrict__ indexes,
                                                     uint8_t *__restrict__ slot_query, uint32_t slot_row_bytes,
                                                     TriSlotMeta *__restrict__ slot_meta,
@@ -32,26 +56,9 @@ __global__ __launch_bounds__(256) void admit_kernel(const TriNewDesc *__restrict
     __shared__ float red[256];
     const TriNewDesc d = desc[blockIdx.x];
     const TriIndexDev &ix = indexes[d.index];
-    const uint8_t *src = rows + d.row_off;
     uint8_t *dst = slot_query + (size_t)d.slot * slot_row_bytes;
-    const uint32_t n16 = ix.row_bytes / 16;
-    float part = 0.f;
-    for (uint32_t c = threadIdx.x; c < n16; c += 256) {
-        const uint4 v = *(const uint4 *)(src + c * 16);
-        *(uint4 *)(dst + c * 16) = v;
-        if (ix.dtype == 1u) {
-            const _Float16 *h = (const _Float16 *)&v;
-#pragma unroll
-            for (int i = 0; i < 8; ++i) {
-                const float f = (float)h[i];
-                part += f * f;
-            }
-        } else {
-            const float *f = (const float *)&v;
-#pragma unroll
-            for (int i = 0; i < 4; ++i) part += f[i] * f[i];
-        }
-    }
+    const float part = ix.dtype == 1u ? admit_row<_Float16>(d, ix.dim, ix.dpad, rows, dst)
+                                      : admit_row<float>(d, ix.dim, ix.dpad, rows, dst);
     red[threadIdx.x] = part;
     __syncthreads();
     for (uint32_t s = 128; s > 0; s >>= 1) {
@@ -65,8 +72,8 @@ __global__ __launch_bounds__(256) void admit_kernel(const TriNewDesc *__restrict
     }
 }
 
-hipError_t tri_launch_admit(const TriLaunchCtx &c, const TriDevWs &ws, const TriNewDesc *desc_dev,
-                            const uint8_t *rows_dev, uint32_t n_new)
+hipError_t tri_launch_admit(const TriLaunchCtx &c, const TriDevWs &ws, const TriNewDesc *desc_dev, uint8_t *rows_dev,
+                            uint32_t n_new)
 {
     if (n_new == 0) return hipSuccess;
     hipLaunchKernelGGL(admit_kernel, dim3(n_new), dim3(256), 0, c.stream, desc_dev, rows_dev, ws.indexes,

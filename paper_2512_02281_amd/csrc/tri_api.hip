@@ -52,6 +52,7 @@ struct Ticket {
     tri_index *index = nullptr;
     uint32_t k = 0, nprobe = 0, metric = 0, klass = 0;
     uint64_t deadline = 0, tag = 0;
+    const void *dev_vec = nullptr;   // non-NULL: the vector is read from device memory at admission
     uint32_t slot = 0;
     uint64_t step_seq = 0;
     uint32_t retire_idx = 0;
@@ -295,6 +296,7 @@ void enqueue_locked(tri_pool *P, const tri_query *q, tri_ticket *out)
     t.index = const_cast<tri_index *>(q->index);
     t.k = q->k; t.nprobe = q->nprobe; t.metric = q->metric; t.klass = q->klass;
     t.deadline = q->deadline_ns; t.tag = q->user_tag;
+    t.dev_vec = nullptr;
     uint8_t *row = &P->qstore[(size_t)ti * P->max_row_bytes];
     const uint32_t es = esize(t.index->p.dtype);
     memcpy(row, q->vec, (size_t)t.index->p.dim * es);
@@ -703,6 +705,42 @@ extern "C" int search_submit_batch(tri_pool *P, const tri_query *q, uint32_t n, 
     return TRI_OK;
 }
 
+extern "C" int search_submit_batch_dev(tri_pool *P, const tri_index *index, const void *vecs, uint64_t pitch_bytes,
+                                       uint32_t n, const uint32_t *k, const uint32_t *nprobe, const uint32_t *metric,
+                                       const uint32_t *klass, tri_ticket *out, uint32_t *n_done)
+{
+    if (n_done) *n_done = 0;
+    if (!P || !index || (n && (!vecs || !k || !nprobe || !metric || !klass || !out))) return fail(TRI_EINVAL, "NULL argument");
+    std::lock_guard<std::mutex> lk(P->mu);
+    const uint32_t es = esize(index->p.dtype);
+    if (pitch_bytes % es || pitch_bytes < (uint64_t)index->p.dim * es || (uintptr_t)vecs % es)
+        return fail(TRI_EINVAL, "pitch_bytes / vecs must be multiples of the element size and cover dim elements");
+    tri_query q{};
+    q.index = index;
+    q.vec = vecs;
+    for (uint32_t i = 0; i < n; ++i) {
+        q.k = k[i]; q.nprobe = nprobe[i]; q.metric = metric[i]; q.klass = klass[i];
+        int rc = validate_query(P, &q);
+        if (rc) return rc;
+    }
+    for (uint32_t i = 0; i < n; ++i) {
+        if (P->free_tickets.empty()) return fail(TRI_EAGAIN, "max_outstanding=%u tickets alive", P->cfg.max_outstanding);
+        const uint32_t ti = P->free_tickets.back();
+        P->free_tickets.pop_back();
+        Ticket &t = P->tickets[ti];
+        t.state = T_PENDING;
+        t.cancelled = false;
+        t.index = const_cast<tri_index *>(index);
+        t.k = k[i]; t.nprobe = nprobe[i]; t.metric = metric[i]; t.klass = klass[i];
+        t.deadline = 0; t.tag = 0;
+        t.dev_vec = (const uint8_t *)vecs + (size_t)i * pitch_bytes;
+        P->pending[t.klass].push_back(ti);
+        out[i] = ((uint64_t)t.gen << 32) | ti;
+        if (n_done) *n_done = i + 1;
+    }
+    return TRI_OK;
+}
+
 extern "C" int search_submit(tri_pool *P, const tri_query *q, tri_ticket *out)
 {
     if (!q || !out) return fail(TRI_EINVAL, "NULL argument");
@@ -797,20 +835,23 @@ extern "C" int search_step(tri_pool *P, tri_step_stats *st)
     // ---- upload block: [descs][plan][rows]
     const size_t plan_bytes = round_up_sz((size_t)n_plan * sizeof(TriPlanEntry), 256);
     uint8_t *rows_h = R.up_host + desc_bytes + plan_bytes;
-    uint32_t row_off = 0;
+    uint32_t row_off = 0, rows_used = 0;
     for (uint32_t i = 0; i < n_new; ++i) {
         const Ticket &t = P->tickets[P->newq[i]];
-        desc_h[i] = TriNewDesc{t.slot, t.index->id, t.metric, t.k, t.nprobe, row_off};
-        memcpy(rows_h + row_off, &P->qstore[(size_t)P->newq[i] * P->max_row_bytes], t.index->row_bytes);
+        desc_h[i] = TriNewDesc{t.slot, t.index->id, t.metric, t.k, t.nprobe, row_off, (uint64_t)(uintptr_t)t.dev_vec};
+        if (!t.dev_vec) {
+            memcpy(rows_h + row_off, &P->qstore[(size_t)P->newq[i] * P->max_row_bytes], t.index->row_bytes);
+            rows_used = row_off + t.index->row_bytes;
+        }
         row_off += t.index->row_bytes;
     }
-    const size_t up_bytes = desc_bytes + plan_bytes + row_off;
+    const size_t up_bytes = desc_bytes + plan_bytes + rows_used;   // rows read from device memory are not uploaded
     hipStream_t s = P->stream;
     const bool prof = (cfg.flags & TRI_FLAG_PROFILE) != 0;
     HIP_TRY(hipMemcpyAsync(P->ws.upload, R.up_host, up_bytes, hipMemcpyHostToDevice, s));
     const TriNewDesc *desc_d = (const TriNewDesc *)P->ws.upload;
     const TriPlanEntry *plan_d = (const TriPlanEntry *)(P->ws.upload + desc_bytes);
-    const uint8_t *rows_d = P->ws.upload + desc_bytes + plan_bytes;
+    uint8_t *rows_d = P->ws.upload + desc_bytes + plan_bytes;
 
     if (prof) HIP_TRY(hipEventRecord(R.ev[0], s));
     HIP_TRY(tri_launch_admit(P->ctx, P->ws, desc_d, rows_d, n_new));
@@ -825,7 +866,7 @@ extern "C" int search_step(tri_pool *P, tri_step_stats *st)
             const uint32_t m = std::min(P->coarse_rows, b - c);
             HIP_TRY(tri_launch_coarse_gemm(s, (int)ix->p.dtype, rows_d + desc_h[c].row_off, ix->row_bytes, m,
                                            ix->dev.centroids, ix->dev.cnorm, ix->p.nlist, ix->row_bytes,
-                                           &desc_d[c].metric, sizeof(TriNewDesc) / 4, 0u, P->ws.coarse_scores, ldc));
+                                           &desc_d[c].metric, (uint32_t)(sizeof(TriNewDesc) / 4), 0u, P->ws.coarse_scores, ldc));
             HIP_TRY(tri_launch_coarse_select(P->ctx, P->ws, desc_d, c, m, ix->p.nlist, ldc));
         }
         a = b;

@@ -37,7 +37,8 @@ struct TriSlotMeta {
 // One admitted query in the step's upload block.
 struct TriNewDesc {
     uint32_t slot, index, metric, k, nprobe;
-    uint32_t row_off;   // byte offset of its padded row inside the uploaded row area
+    uint32_t row_off;   // byte offset of its padded row inside the step's row area
+    uint64_t src_dev;   // 0: the row was uploaded; else device address of the caller's unpadded vector
 };
 
 // One running slot's share of this step.
@@ -114,7 +115,7 @@ struct TriLaunchCtx {
 // ---- launchers (each returns hipGetLastError() of its launches) -----------------------------
 hipError_t tri_launch_fill_u32(hipStream_t s, uint32_t *p, uint32_t v, size_t n);
 hipError_t tri_launch_admit(const TriLaunchCtx &c, const TriDevWs &ws, const TriNewDesc *desc_dev,
-                            const uint8_t *rows_dev, uint32_t n_new);
+                            uint8_t *rows_dev, uint32_t n_new);
 // scores[m][ldc] for m rows (pitch a_pitch_bytes) against n rows of b (pitch row_bytes); the metric
 // is per row (row_metric[m * metric_stride_u32]) or, with row_metric == NULL, fixed_metric.
 hipError_t tri_launch_coarse_gemm(hipStream_t s, int dtype, const void *a_rows, uint32_t a_pitch_bytes,

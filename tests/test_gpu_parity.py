@@ -75,3 +75,296 @@ def test_config0_whole_against_oracle_and_bruteforce():
         ids, dist, n_out, probes, _ = harness.run_all(tri, pool, q)
         rep = harness.compare_with_oracle(oidx, base, queries, cfg.k, cfg.nlist, 0, ids, dist, n_out, probes)
         assert np.array_equal(ids, true_ids), "nprobe = nlist must be exact kNN"
+
+
+def _build_f32(tri, pool, cfg, base, rows):
+    return pool.build_index(base, cfg.dim, cfg.nlist, tri.TRI_F32, tri.TRI_L2, cfg.train_iters, centroids=base[rows])
+
+
+@pytest.mark.parametrize("scale", ["scaled", "full"])
+def test_config1_integer_data_is_bit_exact(scale):
+    """Configuration 1 (byte-valued fp32, d=128): every partial sum is an integer below 2^24, so the
+    fp32 distances must equal the oracle's bit for bit and ties are true ties (strict mode)."""
+    tri = harness.lib()
+    cfg = workloads.CONFIGS[1]
+    if scale == "scaled":
+        cfg = cfg.scaled(n_base=100_000, n_components=128, nlist=128, n_queries=300)
+    _say(f"config 1 {scale}: generate")
+    base, queries, rows = workloads.make_config01(cfg)
+    nprobe = 16 if scale == "scaled" else cfg.nprobe
+    with harness.default_pool(tri, slots=1024, items_per_step=32768, max_dim=cfg.dim, max_nlist=1024,
+                              max_total_lists=1024, score_capacity=96 << 20) as pool:
+        _say(f"config 1 {scale}: build")
+        idx = _build_f32(tri, pool, cfg, base, rows)
+        oidx = harness.oracle_index(tri, idx, base)
+        rep = oindex.check_index(oidx, oracle.METRIC_L2, tol=1e-4, sample=20000, seed=7)
+        _say(f"config 1 {scale}: index check {rep}, longest list {tri.ivf_info(idx)['max_list_len']}")
+        q = tri.make_queries(idx, queries, cfg.k, nprobe, tri.TRI_L2)
+        ids, dist, n_out, probes, stats = harness.run_all(tri, pool, q)
+        _say(f"config 1 {scale}: {len(stats)} steps; compare")
+        rep = harness.compare_with_oracle(oidx, base, queries, cfg.k, nprobe, 0, ids, dist, n_out, probes, strict=True)
+        _say(f"config 1 {scale}: parity {rep}")
+        assert rep["checked"] == cfg.n_queries
+        if scale == "full":
+            sub = np.arange(0, cfg.n_queries, 8)
+            true_ids, _ = bruteforce.knn(base, queries[sub], cfg.k, 0)
+            rec = bruteforce.recall_at_k(ids[sub], true_ids)
+            _say(f"config 1 full: recall@10 = {rec:.4f}")
+            assert rec >= 0.9
+
+
+def _f16_setup(tri, cfg, pool_over=None):
+    import torch
+    base_t, queries_t, rows = workloads.make_config_f16(cfg, device="cuda")
+    torch.cuda.synchronize()
+    base = base_t.cpu().numpy()
+    queries = queries_t.cpu().numpy()
+    return base_t, base, queries, rows
+
+
+@pytest.mark.parametrize("scale", ["scaled", "full"])
+def test_config2_fp16_inner_product_heterogeneous(scale):
+    """Configuration 2: fp16 unit-norm embeddings, inner product, per-query k in {1,10,100} and nprobe
+    in {8..128}.  Full size checks a seeded sample of queries one by one."""
+    tri = harness.lib()
+    cfg = workloads.CONFIGS[2]
+    if scale == "scaled":
+        cfg = cfg.scaled(n_base=60_000, n_components=256, nlist=256, n_queries=200)
+    _say(f"config 2 {scale}: generate")
+    base_t, base, queries, rows = _f16_setup(tri, cfg)
+    k, nprobe = workloads.hetero_params(cfg.n_queries, cfg.seed_params)
+    with harness.default_pool(tri, slots=2048, items_per_step=1 << 18, max_dim=cfg.dim, max_nlist=4096,
+                              max_total_lists=4096, score_capacity=128 << 20) as pool:
+        _say(f"config 2 {scale}: build")
+        idx = pool.build_index(base_t, cfg.dim, cfg.nlist, tri.TRI_F16, tri.TRI_IP, cfg.train_iters,
+                               centroids=base[rows].astype(np.float32))
+        oidx = harness.oracle_index(tri, idx, base)
+        rep = oindex.check_index(oidx, oracle.METRIC_IP, tol=2e-3, sample=5000, seed=7)
+        _say(f"config 2 {scale}: index check {rep}, longest list {tri.ivf_info(idx)['max_list_len']}")
+        q = tri.make_queries(idx, queries, k, nprobe, tri.TRI_IP)
+        ids, dist, n_out, probes, stats = harness.run_all(tri, pool, q)
+        sample = None if scale == "scaled" else np.random.default_rng(5).choice(cfg.n_queries, 96, replace=False)
+        _say(f"config 2 {scale}: {len(stats)} steps; compare")
+        rep = harness.compare_with_oracle(oidx, base, queries, k, nprobe, 1, ids, dist, n_out, probes, sample=sample)
+        _say(f"config 2 {scale}: parity {rep}")
+        # the unit-norm identity: the same queries under L2 return the same neighbours (outside ties)
+        sub = np.arange(0, cfg.n_queries, max(1, cfg.n_queries // 64))[:64]
+        sub_vecs = np.ascontiguousarray(queries[sub])      # must outlive the submit: records hold pointers
+        q2 = tri.make_queries(idx, sub_vecs, 10, 16, tri.TRI_L2)
+        ids2, dist2, n2, probes2, _ = harness.run_all(tri, pool, q2)
+        harness.compare_with_oracle(oidx, base, sub_vecs, 10, 16, 0, ids2, dist2, n2, probes2)
+
+
+def test_scheduling_does_not_change_results():
+    """Continuous batching must leave results intact: one batch, one list per step, a short task
+    array, fewer slots than queries (slot reuse), and mid-stream arrival all give bit-identical
+    ids and scores."""
+    tri = harness.lib()
+    cfg = workloads.CONFIGS[0].scaled(n_base=20_000, n_components=64, nlist=96, n_queries=150)
+    base, queries, rows = workloads.make_config01(cfg)
+    k = np.random.default_rng(1).integers(1, 40, size=cfg.n_queries).astype(np.uint32)
+    nprobe = np.random.default_rng(2).integers(1, 33, size=cfg.n_queries).astype(np.uint32)
+    metric = (np.arange(cfg.n_queries) % 2).astype(np.uint32)
+    variants = {
+        "one batch": dict(pool=dict(), chunks=None),
+        "p=1": dict(pool=dict(lists_per_query_step=1), chunks=None),
+        "p=3, W=64": dict(pool=dict(lists_per_query_step=3, items_per_step=64), chunks=None),
+        "7 slots": dict(pool=dict(slots=7, max_outstanding=256), chunks=None),
+        "mid-stream": dict(pool=dict(lists_per_query_step=2, slots=40), chunks=[1, 5, 20, 3, 50, 1, 1]),
+        "tiny score buffer": dict(pool=dict(score_capacity=2048), chunks=None),
+    }
+    ref = None
+    for name, v in variants.items():
+        _say(f"invariance: {name}")
+        with harness.default_pool(tri, max_dim=cfg.dim, **v["pool"]) as pool:
+            idx = _build_f32(tri, pool, cfg, base, rows)
+            q = tri.make_queries(idx, queries, k, nprobe, metric)
+            ids, dist, n_out, probes, stats = harness.run_all(tri, pool, q, submit_chunks=v["chunks"])
+            _say(f"  {len(stats)} steps")
+            if ref is None:
+                oidx = harness.oracle_index(tri, idx, base)
+                harness.compare_with_oracle(oidx, base, queries, k, nprobe, metric, ids, dist, n_out, probes)
+                ref = (ids, dist, n_out, probes)
+            else:
+                assert np.array_equal(ids, ref[0]), name          # entries past a query's k are -1 / nan
+                assert np.array_equal(dist.view(np.uint32), ref[1].view(np.uint32)), name
+                assert np.array_equal(n_out, ref[2]), name
+                assert all(np.array_equal(a, b) for a, b in zip(probes, ref[3])), name
+
+
+def test_edge_cases():
+    """Short lists (n_out < k), empty lists, nprobe = nlist, k = 1 and k = kmax, a single vector."""
+    tri = harness.lib()
+    rng = np.random.default_rng(11)
+    base = rng.standard_normal((500, 20)).astype(np.float32)
+    cent = rng.standard_normal((12, 20)).astype(np.float32)
+    cent[5] = cent[2]          # duplicated centroid: list 5 is empty (ties go to the smaller number)
+    cent[9] = 1e3              # far away: empty under L2
+    queries = rng.standard_normal((40, 20)).astype(np.float32)
+    with harness.default_pool(tri, max_dim=20, kmax=512, max_nlist=16, max_total_lists=32) as pool:
+        idx = pool.build_index(base, 20, 12, tri.TRI_F32, tri.TRI_L2, 0, centroids=cent)
+        oidx = harness.oracle_index(tri, idx, base)
+        lens = np.diff(oidx.list_off.astype(np.int64))
+        assert lens[5] == 0 and lens[9] == 0
+        oindex.check_index(oidx, 0, tol=1e-5)
+        for k, nprobe in [(1, 1), (512, 1), (512, 12), (7, 12), (100, 3)]:
+            for metric in (0, 1):
+                _say(f"edge: k={k} nprobe={nprobe} metric={metric}")
+                q = tri.make_queries(idx, queries, k, nprobe, metric)
+                ids, dist, n_out, probes, _ = harness.run_all(tri, pool, q)
+                harness.compare_with_oracle(oidx, base, queries, k, nprobe, metric, ids, dist, n_out, probes)
+        # a query aimed at the far centroid probes the empty list first: zero candidates with nprobe=1
+        far = np.full((1, 20), 1e3, dtype=np.float32)
+        q = tri.make_queries(idx, far, 5, 1, tri.TRI_L2)
+        ids, dist, n_out, probes, _ = harness.run_all(tri, pool, q)
+        assert probes[0].tolist() == [9] and n_out[0] == 0 and np.all(ids[0] == -1) and np.all(np.isinf(dist[0]))
+        # one-vector index
+        idx1 = pool.build_index(base[:1], 20, 1, tri.TRI_F32, tri.TRI_L2, 0, centroids=cent[:1])
+        q = tri.make_queries(idx1, queries[:3], 4, 1, tri.TRI_L2)
+        ids, dist, n_out, probes, _ = harness.run_all(tri, pool, q)
+        assert np.all(n_out == 1) and np.all(ids[:, 0] == 0) and np.all(ids[:, 1:] == -1)
+
+
+def test_argument_errors_and_ticket_lifecycle():
+    tri = harness.lib()
+    rng = np.random.default_rng(3)
+    base = rng.standard_normal((300, 16)).astype(np.float32)
+    with harness.default_pool(tri, slots=4, max_dim=16, kmax=16, nprobe_max=8, max_nlist=8, max_total_lists=8,
+                              max_outstanding=6) as pool:
+        idx = pool.build_index(base, 16, 8, tri.TRI_F32, tri.TRI_L2, 2, centroids=None, seed=5)
+        vec = base[0]
+        for kw in (dict(k=0), dict(k=17), dict(nprobe=0), dict(nprobe=9), dict(metric=2), dict(klass=3)):
+            args = dict(k=4, nprobe=2, metric=0, klass=1)
+            args.update(kw)
+            with pytest.raises(tri.TriError) as ei:
+                tri.search_submit(pool.handle, idx, vec, **args)
+            assert ei.value.status == tri.TRI_EINVAL
+        # a step with nothing to do is a no-op
+        st = tri.search_step(pool.handle)
+        assert (st.admitted, st.items, st.running) == (0, 0, 0)
+        # max_outstanding tickets, then EAGAIN
+        first8 = np.ascontiguousarray(base[:8])
+        qs = tri.make_queries(idx, first8, 4, 2, 0)
+        tickets, rc = tri.search_submit_batch(pool.handle, qs)
+        assert rc == tri.TRI_EAGAIN and tickets.shape[0] == 6
+        assert tri.search_poll(pool.handle, int(tickets[0]), 4) is None        # queued, not finished
+        tri.search_cancel(pool.handle, int(tickets[1]))                         # cancel while queued
+        st = tri.search_step(pool.handle)
+        assert st.admitted == 4 and st.pending_low == 1
+        tri.search_cancel(pool.handle, int(tickets[2]))                         # cancel while running
+        while True:
+            st = tri.search_step(pool.handle)
+            if st.running == 0 and st.pending_low == 0 and st.items == 0:
+                break
+        tri.search_sync(pool.handle)
+        for i in (1, 2):
+            with pytest.raises(tri.TriError) as ei:
+                tri.search_poll(pool.handle, int(tickets[i]), 4)
+            assert ei.value.status == tri.TRI_ENOENT
+        for i in (0, 3, 4, 5):
+            ids, dist, n = tri.search_poll(pool.handle, int(tickets[i]), 4)
+            assert n == 4 and ids[0] == i          # the query is a base row: its own nearest neighbour
+        with pytest.raises(tri.TriError) as ei:                                 # consumed
+            tri.search_poll(pool.handle, int(tickets[0]), 4)
+        assert ei.value.status == tri.TRI_ENOENT
+
+
+def test_two_indexes_two_classes():
+    """A pool with an fp16/IP index and an fp32/L2 index; with a saturated slot table a later
+    high-class query is admitted before earlier low-class ones."""
+    tri = harness.lib()
+    cfg_a = workloads.CONFIGS[2].scaled(n_base=20_000, n_components=64, nlist=64, n_queries=60)
+    cfg_b = workloads.CONFIGS[0].scaled(n_base=5_000, n_components=16, nlist=32, n_queries=60, dim=40)
+    base_a_t, base_a, queries_a, rows_a = _f16_setup(tri, cfg_a)
+    base_b, queries_b, rows_b = workloads.make_config01(cfg_b)
+    with harness.default_pool(tri, slots=8, max_dim=768, max_outstanding=512, lists_per_query_step=4) as pool:
+        ia = pool.build_index(base_a_t, cfg_a.dim, cfg_a.nlist, tri.TRI_F16, tri.TRI_IP, 5,
+                              centroids=base_a[rows_a].astype(np.float32))
+        ib = pool.build_index(base_b, cfg_b.dim, cfg_b.nlist, tri.TRI_F32, tri.TRI_L2, 5, centroids=base_b[rows_b])
+        oa, ob = harness.oracle_index(tri, ia, base_a), harness.oracle_index(tri, ib, base_b)
+        qa = tri.make_queries(ia, queries_a, 10, 16, tri.TRI_IP, tri.TRI_CLASS_LOW)
+        qb = tri.make_queries(ib, queries_b, 5, 8, tri.TRI_L2, tri.TRI_CLASS_LOW)
+        mixed = np.concatenate([qa, qb])
+        order = np.random.default_rng(9).permutation(mixed.shape[0])
+        ids, dist, n_out, probes, stats = harness.run_all(tri, pool, np.ascontiguousarray(mixed[order]),
+                                                          submit_chunks=[10, 30, 5])
+        inv = np.argsort(order)
+        ids, dist, n_out = ids[inv], dist[inv], n_out[inv]
+        probes = [probes[i] for i in inv]
+        harness.compare_with_oracle(oa, base_a, queries_a, 10, 16, 1, ids[:60], dist[:60], n_out[:60], probes[:60])
+        harness.compare_with_oracle(ob, base_b, queries_b, 5, 8, 0, ids[60:], dist[60:], n_out[60:], probes[60:])
+        # priority: fill the table and the low queue, then submit one high-class query
+        low, _ = tri.search_submit_batch(pool.handle, np.ascontiguousarray(qa[:30]))
+        tri.search_step(pool.handle)                       # 8 low-class queries running, 22 waiting
+        high = tri.search_submit(pool.handle, ia, queries_a[0], 10, 16, tri.TRI_IP, tri.TRI_CLASS_HIGH)
+        done_at = {}
+        for step in range(1, 400):
+            st = tri.search_step(pool.handle)
+            tri.search_sync(pool.handle)
+            for name, t in [("high", high)] + [(f"low{i}", int(t)) for i, t in enumerate(low)]:
+                if name not in done_at and tri.search_poll(pool.handle, t, 10) is not None:
+                    done_at[name] = step
+            if len(done_at) == 31:
+                break
+        assert len(done_at) == 31
+        # the high-class query takes the first slot that frees: none of the 22 low-class queries that were
+        # waiting before it finishes earlier; those not admitted at that same boundary finish strictly later
+        assert all(done_at[f"low{i}"] >= done_at["high"] for i in range(8, 30))
+        later = sum(1 for i in range(8, 30) if done_at[f"low{i}"] > done_at["high"])
+        assert later >= 22 - 7, f"only {later} of the 22 waiting low-class queries finished after the high-class one"
+
+
+@pytest.mark.timeout(900)
+def test_config4_full_size_in_the_benchmark_configuration():
+    """Configuration 4 at full size (10M x 768 fp16, nlist 16384, 4096 queries, nprobe 64, k 100) in
+    the launch configuration the benchmark times (4096 slots, one step per batch, device-resident
+    query vectors): a seeded sample of queries is checked one by one against the oracle, every
+    query against the properties that hold at any size."""
+    import torch
+    tri = harness.lib()
+    cfg = workloads.CONFIGS[4]
+    _say("config 4: generate")
+    base_t, queries_t, rows = workloads.make_config_f16(cfg, device="cuda")
+    torch.cuda.synchronize()
+    Q = cfg.n_queries
+    pool = tri.Pool(slots=Q, items_per_step=Q * cfg.nprobe, lists_per_query_step=0, kmax=128, nprobe_max=cfg.nprobe,
+                    max_indexes=1, max_total_lists=cfg.nlist, max_nlist=cfg.nlist, max_dim=cfg.dim,
+                    max_outstanding=Q * 2, coarse_rows=0, flags=tri.TRI_FLAG_KEEP_PROBES, score_capacity=(1 << 30))
+    try:
+        _say("config 4: build")
+        init = base_t[torch.from_numpy(rows).cuda()].float().cpu().numpy()
+        idx = pool.build_index(base_t, cfg.dim, cfg.nlist, tri.TRI_F16, tri.TRI_IP, cfg.train_iters, centroids=init)
+        _say(f"config 4: built, longest list {tri.ivf_info(idx)['max_list_len']}; search")
+        tickets, rc = tri.search_submit_batch_dev(pool.handle, idx, queries_t.data_ptr(), cfg.dim * 2, Q, cfg.k,
+                                                  cfg.nprobe, tri.TRI_IP)
+        assert rc == tri.TRI_OK
+        st = tri.search_step(pool.handle)
+        assert st.admitted == Q and st.retired == Q and st.items == Q * cfg.nprobe     # one launch per batch
+        tri.search_sync(pool.handle)
+        sample = np.sort(np.random.default_rng(44).choice(Q, 40, replace=False))
+        probes = [None] * Q
+        for i in sample:
+            probes[i] = tri.search_probes(pool.handle, int(tickets[i]), cfg.nprobe)
+        ids, dist, n_out, status = tri.search_poll_batch(pool.handle, tickets, cfg.k)
+        assert np.all(status == tri.TRI_OK)
+        # properties for every query
+        assert np.all(n_out == cfg.k)
+        assert ids.min() >= 0 and ids.max() < cfg.n_base
+        assert np.all(np.diff(dist, axis=1) <= 0), "inner-product scores must be descending"
+        srt = np.sort(ids, axis=1)
+        assert np.all(srt[:, 1:] != srt[:, :-1]), "duplicate ids in a result"
+        _say("config 4: copy the base to the host, export, compare the sample with the oracle")
+        base = base_t.cpu().numpy()
+        queries = queries_t.cpu().numpy()
+        oidx = harness.oracle_index(tri, idx, base)
+        rep = oindex.check_index(oidx, oracle.METRIC_IP, tol=2e-3, sample=512, seed=3)
+        _say(f"config 4: index check {rep}")
+        rep = harness.compare_with_oracle(oidx, base, queries, cfg.k, cfg.nprobe, 1, ids, dist, n_out, probes,
+                                          sample=sample)
+        _say(f"config 4: parity {rep}")
+        # returned scores of ALL queries against fp64 dot products of the stored vectors
+        for i in range(0, Q, 97):
+            want = base[ids[i]].astype(np.float64) @ queries[i].astype(np.float64)
+            assert np.all(np.abs(dist[i] - want) <= 2e-3 * np.abs(want) + checker.ABS_EPS)
+    finally:
+        pool.close()

@@ -1,0 +1,121 @@
+"""CPU-only checks of the C-ABI library: it loads, exports every function the header declares,
+its structs have the layout the binding assumes, and the host-only entry points validate their
+arguments.  No GPU work is launched here."""
+import ctypes
+import os
+import re
+import subprocess
+import tempfile
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = os.path.join(ROOT, "include", "trinity_ivf.h")
+
+
+@pytest.fixture(scope="module")
+def tri():
+    lib_path = os.path.join(ROOT, "paper_2512_02281_amd", "libtrinity_ivf.so")
+    if not os.path.exists(lib_path):
+        from paper_2512_02281_amd.build import build_library
+        build_library()
+    import paper_2512_02281_amd as tri
+    return tri
+
+
+def _declared_functions():
+    text = open(HEADER).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    names = re.findall(r"^\s*(?:const\s+char\s*\*\s*|int\s+)(\w+)\s*\(", text, flags=re.M)
+    return sorted(set(names))
+
+
+def test_library_exports_every_declared_function(tri):
+    declared = _declared_functions()
+    assert len(declared) >= 20
+    lib = ctypes.CDLL(tri.LIB_PATH)
+    for name in declared:
+        assert hasattr(lib, name), f"{name} is declared in the header but not exported"
+    assert sorted(tri.EXPORTS) == declared, "binding and header disagree on the entry points"
+    for name in ("ivf_build", "search_submit", "search_step", "search_poll"):
+        assert name in declared
+    assert "gfx950" in tri.tri_version()
+
+
+def test_struct_layouts_match_the_header(tri):
+    prog = r'''
+#include <stdio.h>
+#include <stddef.h>
+#include "trinity_ivf.h"
+int main(void) {
+  printf("%zu %zu %zu %zu %zu\n", sizeof(tri_pool_cfg), sizeof(ivf_params), sizeof(tri_query),
+         sizeof(tri_step_stats), sizeof(tri_kernel_times));
+  printf("%zu %zu %zu %zu\n", offsetof(tri_pool_cfg, score_capacity), offsetof(tri_pool_cfg, hip_stream),
+         offsetof(ivf_params, seed), offsetof(tri_query, deadline_ns));
+  return 0;
+}'''
+    with tempfile.TemporaryDirectory() as tmp:
+        src, exe = os.path.join(tmp, "a.c"), os.path.join(tmp, "a.out")
+        open(src, "w").write(prog)
+        subprocess.check_call(["gcc", "-std=c99", "-I", os.path.join(ROOT, "include"), "-o", exe, src])
+        out = subprocess.check_output([exe]).decode().split()
+    sizes = [int(v) for v in out]
+    assert sizes[:5] == [ctypes.sizeof(tri.tri_pool_cfg), ctypes.sizeof(tri.ivf_params), ctypes.sizeof(tri.tri_query),
+                         ctypes.sizeof(tri.tri_step_stats), ctypes.sizeof(tri.tri_kernel_times)]
+    assert sizes[5:] == [tri.tri_pool_cfg.score_capacity.offset, tri.tri_pool_cfg.hip_stream.offset,
+                         tri.ivf_params.seed.offset, tri.tri_query.deadline_ns.offset]
+
+
+def _cfg(tri, **over):
+    base = dict(slots=64, items_per_step=1024, lists_per_query_step=0, kmax=100, nprobe_max=64, max_indexes=2,
+                max_total_lists=2048, max_nlist=1024, max_dim=768, max_outstanding=256, coarse_rows=0, flags=0,
+                score_capacity=0)
+    base.update(over)
+    return tri.tri_pool_cfg(**base)
+
+
+def test_workspace_size_and_config_validation(tri):
+    small = tri.tri_pool_workspace_bytes(_cfg(tri))
+    big = tri.tri_pool_workspace_bytes(_cfg(tri, slots=4096, items_per_step=1 << 18, max_outstanding=8192))
+    assert 0 < small < big and small % 256 == 0
+    # the score buffer dominates: W * 1024 floats by default
+    assert big > (1 << 18) * 1024 * 4
+    for bad in (dict(slots=0), dict(items_per_step=0), dict(kmax=0), dict(kmax=2000), dict(nprobe_max=0),
+                dict(nprobe_max=5000), dict(max_indexes=0), dict(max_nlist=0), dict(max_total_lists=10),
+                dict(max_dim=0), dict(max_dim=4096), dict(max_outstanding=8)):
+        with pytest.raises(tri.TriError) as ei:
+            tri.tri_pool_workspace_bytes(_cfg(tri, **bad))
+        assert ei.value.status == tri.TRI_EINVAL and tri.tri_last_error()
+
+
+def test_index_size_and_parameter_validation(tri):
+    p = tri.ivf_params(768, 1024, tri.TRI_F16, tri.TRI_IP, 10, 1)
+    n = 100_000
+    got = tri.ivf_build_bytes(p, n)
+    assert got >= n * 768 * 2 + n * 8 + 1024 * 768 * 2           # vectors + norms + ids + centroids
+    assert got < n * 768 * 2 * 1.02 + (1 << 20)
+    p32 = tri.ivf_params(100, 16, tri.TRI_F32, tri.TRI_L2, 0, 0)   # dim 100 fp32 pads to 128 elements
+    assert tri.ivf_build_bytes(p32, 1000) >= 1000 * 128 * 4
+    for bad, nn in ((tri.ivf_params(0, 4, 0, 0, 0, 0), 10), (tri.ivf_params(8, 0, 0, 0, 0, 0), 10),
+                    (tri.ivf_params(8, 4, 7, 0, 0, 0), 10), (tri.ivf_params(8, 4, 0, 0, 0, 0), 0),
+                    (tri.ivf_params(8, 40, 0, 0, 0, 0), 10), (tri.ivf_params(5000, 4, 1, 0, 0, 0), 10),
+                    (tri.ivf_params(8, 4, 0, 0, 0, 0), 1 << 33)):
+        with pytest.raises(tri.TriError) as ei:
+            tri.ivf_build_bytes(bad, nn)
+        assert ei.value.status == tri.TRI_EINVAL
+
+
+def test_product_path_never_touches_the_oracle():
+    """The library sources and the binding must not reference the oracle (no CPU fallback)."""
+    pkg = os.path.join(ROOT, "paper_2512_02281_amd")
+    for dirpath, _, files in os.walk(pkg):
+        if "_build" in dirpath:
+            continue
+        for f in files:
+            if f.endswith((".py", ".hip", ".h", ".cpp")):
+                text = open(os.path.join(dirpath, f)).read()
+                assert "oracle" not in text.lower(), f"{f} mentions the oracle"
+    for f in os.listdir(os.path.join(ROOT, "oracle")):
+        if f.endswith((".py", ".c")):
+            text = open(os.path.join(ROOT, "oracle", f)).read()
+            assert "paper_2512_02281_amd" not in text and "trinity_ivf" not in text
