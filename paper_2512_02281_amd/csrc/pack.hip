@@ -108,10 +108,12 @@ __global__ void pack_emit_kernel(const TriPlanEntry *__restrict__ plan, uint32_t
     item_rank[i] = atomicAdd(&hist[g], 1u);
 }
 
-// (2) scan: one workgroup.  Exclusive prefix sums over the pool-wide list table of: items per list
-//     (-> list_start), tiles per list (-> tile_base), padded scores per list (-> score_base).
-//     Also the step totals and the reset of the scan kernel's work-queue head.
-__global__ __launch_bounds__(1024) void pack_scan_kernel(const uint32_t *__restrict__ hist, uint32_t total_lists,
+// (2) scan: one workgroup.  Exclusive prefix sums, taken over the attached lists in the order of
+//     descending byte length (so the longest tiles are dealt out first and the step ends on the
+//     shortest), of: items per list (-> list_start), tiles per list (-> tile_base), padded scores
+//     per list (-> score_base).  Also the step totals and the reset of the work-queue heads.
+__global__ __launch_bounds__(1024) void pack_scan_kernel(const uint32_t *__restrict__ hist, uint32_t n_order,
+                                                         const uint32_t *__restrict__ glist_order,
                                                          const uint32_t *__restrict__ glist_len,
                                                          const uint32_t *__restrict__ glist_index,
                                                          const TriIndexDev *__restrict__ indexes,
@@ -119,23 +121,24 @@ __global__ __launch_bounds__(1024) void pack_scan_kernel(const uint32_t *__restr
                                                          uint32_t *__restrict__ tile_base,
                                                          uint64_t *__restrict__ score_base,
                                                          TriStepDev *__restrict__ step_dev,
-                                                         uint32_t *__restrict__ tile_counter)
+                                                         uint32_t *__restrict__ tile_counter, uint32_t chunk_vecs)
 {
     __shared__ uint32_t s_items[1024], s_tiles[1024], s_lists[1024];
     __shared__ uint64_t s_scores[1024], s_tbytes[1024], s_ubytes[1024];
     const uint32_t t = threadIdx.x;
-    const uint32_t per = (total_lists + 1023) / 1024;
-    const uint32_t g0 = t * per, g1 = min(g0 + per, total_lists);
+    const uint32_t per = (n_order + 1023) / 1024;
+    const uint32_t i0 = min(t * per, n_order), i1 = min(i0 + per, n_order);
     uint32_t items = 0, tiles = 0, lists = 0;
     uint64_t sc = 0, tb = 0, ub = 0;
-    for (uint32_t g = g0; g < g1; ++g) {
+    for (uint32_t i = i0; i < i1; ++i) {
+        const uint32_t g = glist_order[i];
         const uint32_t c = hist[g];
         if (c) {
             const uint32_t len = glist_len[g];
             const uint32_t nt = (c + TRI_QT - 1) / TRI_QT;
             const uint64_t bytes = (uint64_t)len * indexes[glist_index[g]].row_bytes;
             items += c;
-            tiles += nt;
+            tiles += nt * ((len + chunk_vecs - 1) / chunk_vecs);
             lists += 1;
             sc += (uint64_t)c * ((len + TRI_VB - 1) / TRI_VB * TRI_VB);
             tb += bytes * nt;
@@ -160,7 +163,8 @@ __global__ __launch_bounds__(1024) void pack_scan_kernel(const uint32_t *__restr
     }
     uint32_t it = s_items[t] - items, ti = s_tiles[t] - tiles;
     uint64_t so = s_scores[t] - sc;
-    for (uint32_t g = g0; g < g1; ++g) {
+    for (uint32_t i = i0; i < i1; ++i) {
+        const uint32_t g = glist_order[i];
         const uint32_t c = hist[g];
         list_start[g] = it;
         tile_base[g] = ti;
@@ -168,7 +172,7 @@ __global__ __launch_bounds__(1024) void pack_scan_kernel(const uint32_t *__restr
         if (c) {
             const uint32_t len = glist_len[g];
             it += c;
-            ti += (c + TRI_QT - 1) / TRI_QT;
+            ti += (c + TRI_QT - 1) / TRI_QT * ((len + chunk_vecs - 1) / chunk_vecs);
             so += (uint64_t)c * ((len + TRI_VB - 1) / TRI_VB * TRI_VB);
         }
     }
@@ -178,7 +182,7 @@ __global__ __launch_bounds__(1024) void pack_scan_kernel(const uint32_t *__restr
         step_dev->total_scores = s_scores[t];
         step_dev->tile_vec_bytes = s_tbytes[t];
         step_dev->unique_vec_bytes = s_ubytes[t];
-        *tile_counter = 0;
+        for (uint32_t k = 0; k < TRI_SCAN_CLASSES; ++k) tile_counter[k] = 0;
     }
 }
 
@@ -197,31 +201,47 @@ __global__ void pack_scatter_kernel(uint32_t n_items, const uint32_t *__restrict
     item_score_off[i] = score_base[g] + (uint64_t)r * npad;
 }
 
-// (4) tiles: one thread per list of the pool-wide table.
+// (4) tiles: one thread per list of the pool-wide table.  A list longer than chunk_vecs is cut into
+//     chunks; the tiles of one chunk (one per group of TRI_QT queries) are adjacent in the queue.
 __global__ void pack_tiles_kernel(uint32_t total_lists, const uint32_t *__restrict__ hist,
                                   const uint32_t *__restrict__ list_start, const uint32_t *__restrict__ tile_base,
                                   const uint64_t *__restrict__ score_base, const uint32_t *__restrict__ glist_len,
+                                  const uint32_t *__restrict__ glist_voff, const uint32_t *__restrict__ glist_index,
+                                  const TriIndexDev *__restrict__ indexes, uint32_t chunk_vecs,
                                   TriTile *__restrict__ tiles)
 {
     const uint32_t g = blockIdx.x * blockDim.x + threadIdx.x;
     if (g >= total_lists) return;
     const uint32_t c = hist[g];
-    if (!c) return;
-    const uint32_t npad = (glist_len[g] + TRI_VB - 1) / TRI_VB * TRI_VB;
+    const uint32_t len = glist_len[g];
+    if (!c || !len) return;
+    const TriIndexDev &ix = indexes[glist_index[g]];
+    const uint32_t npad = (len + TRI_VB - 1) / TRI_VB * TRI_VB;
     const uint32_t nt = (c + TRI_QT - 1) / TRI_QT;
-    for (uint32_t q = 0; q < nt; ++q) {
-        TriTile tl;
-        tl.glist = g;
-        tl.item_pos = list_start[g] + q * TRI_QT;
-        tl.nq = min((uint32_t)TRI_QT, c - q * TRI_QT);
-        tl.pad_ = 0;
-        tl.score_off = score_base[g] + (uint64_t)q * TRI_QT * npad;
-        tiles[tile_base[g] + q] = tl;
+    const uint32_t nchunks = (len + chunk_vecs - 1) / chunk_vecs;
+    const uint32_t voff = glist_voff[g];
+    uint32_t w = tile_base[g];
+    for (uint32_t ch = 0; ch < nchunks; ++ch) {
+        const uint32_t v0 = ch * chunk_vecs;
+        for (uint32_t q = 0; q < nt; ++q) {
+            TriTile tl;
+            tl.vec_addr = (uint64_t)(uintptr_t)ix.vecs + (uint64_t)(voff + v0) * ix.row_bytes;
+            tl.vnorm_addr = (uint64_t)(uintptr_t)(ix.vnorm + voff + v0);
+            tl.score_off = score_base[g] + (uint64_t)q * TRI_QT * npad + v0;
+            tl.item_pos = list_start[g] + q * TRI_QT;
+            tl.nq = min((uint32_t)TRI_QT, c - q * TRI_QT);
+            tl.vec_count = min(chunk_vecs, len - v0);
+            tl.npad = npad;
+            tl.klass = tri_scan_class(ix.dtype, ix.row_bytes);
+            tl.row_bytes = ix.row_bytes;
+            tl.pad_[0] = tl.pad_[1] = 0;
+            tiles[w++] = tl;
+        }
     }
 }
 
 hipError_t tri_launch_pack(const TriLaunchCtx &c, const TriDevWs &ws, const TriPlanEntry *plan_dev, uint32_t n_plan,
-                           uint32_t n_items, uint32_t total_lists)
+                           uint32_t n_items, uint32_t total_lists, uint32_t n_order, uint32_t chunk_vecs)
 {
     if (n_items == 0 || total_lists == 0) return hipSuccess;
     hipError_t e = tri_launch_fill_u32(c.stream, ws.hist, 0u, total_lists);
@@ -229,13 +249,14 @@ hipError_t tri_launch_pack(const TriLaunchCtx &c, const TriDevWs &ws, const TriP
     hipLaunchKernelGGL(pack_emit_kernel, dim3((n_items + 255) / 256), dim3(256), 0, c.stream, plan_dev, n_plan,
                        n_items, ws.slot_meta, ws.indexes, ws.probe, c.nprobe_max, ws.item_glist, ws.item_slot,
                        ws.item_rank, ws.hist);
-    hipLaunchKernelGGL(pack_scan_kernel, dim3(1), dim3(1024), 0, c.stream, ws.hist, total_lists, ws.glist_len,
+    hipLaunchKernelGGL(pack_scan_kernel, dim3(1), dim3(1024), 0, c.stream, ws.hist, n_order, ws.glist_order, ws.glist_len,
                        ws.glist_index, ws.indexes, ws.list_start, ws.tile_base, ws.score_base, ws.step_dev,
-                       ws.tile_counter);
+                       ws.tile_counter, chunk_vecs);
     hipLaunchKernelGGL(pack_scatter_kernel, dim3((n_items + 255) / 256), dim3(256), 0, c.stream, n_items,
                        ws.item_glist, ws.item_slot, ws.item_rank, ws.list_start, ws.score_base, ws.glist_len,
                        ws.sorted_slot, ws.item_score_off);
     hipLaunchKernelGGL(pack_tiles_kernel, dim3((total_lists + 255) / 256), dim3(256), 0, c.stream, total_lists,
-                       ws.hist, ws.list_start, ws.tile_base, ws.score_base, ws.glist_len, ws.tiles);
+                       ws.hist, ws.list_start, ws.tile_base, ws.score_base, ws.glist_len, ws.glist_voff, ws.glist_index,
+                       ws.indexes, chunk_vecs, ws.tiles);
     return hipGetLastError();
 }

@@ -91,6 +91,7 @@ struct tri_index {
     TriIndexDev dev{};
     uint32_t *ids_dev = nullptr;
     uint32_t *list_off_dev = nullptr;
+    std::vector<uint32_t> list_len;   // host copy of the list lengths
 };
 
 struct tri_pool {
@@ -102,6 +103,9 @@ struct tri_pool {
     TriLaunchCtx ctx{};
     uint32_t max_row_bytes = 0, coarse_rows = 0, coarse_ldc = 0;
     uint32_t attached_row_bytes = 128;   // widest row among the attached indexes (sizes the scan kernel's LDS)
+    uint32_t scan_class_mask = 0;        // scan kernel variants the attached indexes need
+    uint32_t n_order = 0;                // attached lists (entries of the device-side scan order)
+    uint32_t chunk_vecs = 1024;          // lists longer than this are scanned as several tiles (at most 4)
     uint64_t score_capacity = 0;
     size_t upload_bytes = 0, down_bytes = 0;
     size_t down_probe_off = 0, down_step_off = 0;
@@ -154,6 +158,7 @@ size_t carve(const tri_pool_cfg &c, uint32_t max_row_bytes, uint32_t coarse_rows
     CARVE(glist_len, uint32_t *, G * 4)
     CARVE(glist_voff, uint32_t *, G * 4)
     CARVE(glist_index, uint32_t *, G * 4)
+    CARVE(glist_order, uint32_t *, G * 4)
     CARVE(upload, uint8_t *, upload_bytes)
     CARVE(coarse_scores, float *, (size_t)coarse_rows * coarse_ldc * 4)
     CARVE(item_glist, uint32_t *, W * 4)
@@ -165,7 +170,7 @@ size_t carve(const tri_pool_cfg &c, uint32_t max_row_bytes, uint32_t coarse_rows
     CARVE(list_start, uint32_t *, G * 4)
     CARVE(tile_base, uint32_t *, G * 4)
     CARVE(score_base, uint64_t *, G * 8)
-    CARVE(tiles, TriTile *, W * sizeof(TriTile))
+    CARVE(tiles, TriTile *, (size_t)TRI_TILES_PER_ITEM * W * sizeof(TriTile))
     CARVE(tile_counter, uint32_t *, 256)
     CARVE(step_dev, TriStepDev *, 256)
     CARVE(scores, float *, (size_t)score_capacity * 4)
@@ -193,6 +198,8 @@ int derive(const tri_pool_cfg *c, uint32_t *max_row_bytes, uint32_t *coarse_rows
     const uint32_t rb16 = round_up(c->max_dim * 2u, 128u);
     if (rb16 > TRI_MAX_ROW_BYTES) return fail(TRI_EINVAL, "max_dim too large: padded fp16 row exceeds %u bytes", TRI_MAX_ROW_BYTES);
     *max_row_bytes = rb > TRI_MAX_ROW_BYTES ? TRI_MAX_ROW_BYTES : rb;
+    if ((uint64_t)c->slots * *max_row_bytes >= (1ull << 31))
+        return fail(TRI_EINVAL, "slots * padded row bytes must stay below 2^31");
     *coarse_rows = c->coarse_rows ? c->coarse_rows : 1024u;
     if (*coarse_rows > c->slots) *coarse_rows = c->slots;
     *coarse_ldc = round_up(c->max_nlist, 32u);
@@ -262,6 +269,29 @@ int reap(tri_pool *P, bool block, uint32_t *finished)
         R->in_use = false;
     }
     if (finished) *finished += fin;
+    return TRI_OK;
+}
+
+// Scan order of the pool-wide list table: every attached list, longest (in bytes) first.
+int upload_scan_order(tri_pool *P)
+{
+    std::vector<std::pair<uint64_t, uint32_t>> v;
+    for (tri_index *ix : P->indexes)
+        if (ix)
+            for (uint32_t l = 0; l < ix->p.nlist; ++l)
+                v.emplace_back((uint64_t)ix->list_len[l] * ix->row_bytes, ix->list_base + l);
+    std::stable_sort(v.begin(), v.end(), [](const std::pair<uint64_t, uint32_t> &a, const std::pair<uint64_t, uint32_t> &b) {
+        return a.first > b.first;
+    });
+    std::vector<uint32_t> order(v.size());
+    for (size_t i = 0; i < v.size(); ++i) order[i] = v[i].second;
+    if (!order.empty())
+        HIP_TRY(hipMemcpy(P->ws.glist_order, order.data(), order.size() * 4, hipMemcpyHostToDevice));
+    P->n_order = (uint32_t)order.size();
+    uint32_t longest = 0;
+    for (tri_index *ix : P->indexes)
+        if (ix) longest = std::max(longest, ix->max_list_len);
+    P->chunk_vecs = std::max(1024u, round_up((longest + TRI_TILES_PER_ITEM - 1) / TRI_TILES_PER_ITEM, TRI_VB));
     return TRI_OK;
 }
 
@@ -381,8 +411,6 @@ extern "C" int tri_pool_create(const tri_pool_cfg *cfg, void *dev_ws, size_t dev
         tri_pool_destroy(P);
         return fail(TRI_ENOMEM, "out of host memory");
     }
-    e = tri_scan_configure(mrb);
-    if (e != hipSuccess) { tri_pool_destroy(P); return fail(TRI_EHIP, "scan kernel LDS limit -> %s", hipGetErrorString(e)); }
     *out = P;
     return TRI_OK;
 }
@@ -606,6 +634,8 @@ extern "C" int ivf_build(tri_pool *P, const ivf_params *p, const void *base, uin
     uint32_t maxlen = 0;
     std::vector<uint32_t> h_len(nlist), h_idx(nlist, id);
     for (uint32_t l = 0; l < nlist; ++l) { h_len[l] = h_off[l + 1] - h_off[l]; maxlen = std::max(maxlen, h_len[l]); }
+    if ((uint64_t)maxlen * rb >= (1ull << 31))
+        return fail(TRI_EINVAL, "longest list (%u vectors of %u bytes) exceeds 2^31 bytes", maxlen, rb);
     if ((uint64_t)round_up(maxlen, TRI_VB) > P->score_capacity)
         return fail(TRI_ENOMEM, "longest list (%u) exceeds the pool's score capacity", maxlen);
     tri_index *ix = new (std::nothrow) tri_index();
@@ -618,9 +648,13 @@ extern "C" int ivf_build(tri_pool *P, const ivf_params *p, const void *base, uin
     if (e == hipSuccess) e = hipMemcpy(P->ws.glist_voff + ix->list_base, h_off.data(), (size_t)nlist * 4, hipMemcpyHostToDevice);
     if (e == hipSuccess) e = hipMemcpy(P->ws.glist_index + ix->list_base, h_idx.data(), (size_t)nlist * 4, hipMemcpyHostToDevice);
     if (e != hipSuccess) { delete ix; return fail(TRI_EHIP, "attach copy -> %s", hipGetErrorString(e)); }
+    ix->list_len = h_len;
     P->indexes[id] = ix;
+    rc = upload_scan_order(P);
+    if (rc) { P->indexes[id] = nullptr; delete ix; return rc; }
     P->total_lists += nlist;
     P->attached_row_bytes = std::max(P->attached_row_bytes, rb);
+    P->scan_class_mask |= 1u << tri_scan_class(p->dtype, rb);
     *out = ix;
     return TRI_OK;
 }
@@ -678,11 +712,15 @@ extern "C" int ivf_destroy(tri_index *ix)
     // finished, unpolled tickets of this index stay valid: their results are already on the host
     P->indexes[ix->id] = nullptr;
     P->attached_row_bytes = 128;
+    P->scan_class_mask = 0;
     for (tri_index *o : P->indexes)
-        if (o) P->attached_row_bytes = std::max(P->attached_row_bytes, o->row_bytes);
+        if (o) {
+            P->attached_row_bytes = std::max(P->attached_row_bytes, o->row_bytes);
+            P->scan_class_mask |= 1u << tri_scan_class(o->p.dtype, o->row_bytes);
+        }
     if (ix->list_base + ix->p.nlist == P->total_lists) P->total_lists = ix->list_base;   // last attached: give its list range back
     delete ix;
-    return TRI_OK;
+    return upload_scan_order(P);
 }
 
 // ================================================================================== search
@@ -872,9 +910,9 @@ extern "C" int search_step(tri_pool *P, tri_step_stats *st)
         a = b;
     }
     if (prof) HIP_TRY(hipEventRecord(R.ev[2], s));
-    HIP_TRY(tri_launch_pack(P->ctx, P->ws, plan_d, n_plan, n_items, P->total_lists));
+    HIP_TRY(tri_launch_pack(P->ctx, P->ws, plan_d, n_plan, n_items, P->total_lists, P->n_order, P->chunk_vecs));
     if (prof) HIP_TRY(hipEventRecord(R.ev[3], s));
-    if (n_items) HIP_TRY(tri_launch_scan(P->ctx, P->ws, P->attached_row_bytes));
+    if (n_items) HIP_TRY(tri_launch_scan(P->ctx, P->ws, P->attached_row_bytes, P->scan_class_mask));
     if (prof) HIP_TRY(hipEventRecord(R.ev[4], s));
     HIP_TRY(tri_launch_merge(P->ctx, P->ws, plan_d, n_plan, (cfg.flags & TRI_FLAG_KEEP_PROBES) != 0));
     if (n_retire) {

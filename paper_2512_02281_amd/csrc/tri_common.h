@@ -8,6 +8,7 @@
 #define TRI_VB 32            // vectors per scan block (rows of one MFMA output block)
 #define TRI_SEL_THREADS 256  // threads of a selection workgroup
 #define TRI_SCAN_THREADS 256 // threads of a scan workgroup (4 wavefronts)
+#define TRI_SCAN_CLASSES 10  // scan kernel variants: 2 storage types x (generic + 4 row lengths)
 #define TRI_KMAX_POW2 1024   // largest k (and nprobe) a selection can return
 
 // One attached index as the kernels see it.  All pointers are device pointers.
@@ -51,13 +52,19 @@ struct TriPlanEntry {
     uint32_t pad_;
 };
 
-// One scan tile: up to TRI_QT queries against one whole inverted list.
+// One scan tile: up to TRI_QT queries against one chunk (all of it, for short lists) of one inverted
+// list.  Self-contained: the scan kernels read nothing else about the list.
 struct TriTile {
-    uint32_t glist;      // pool-wide list number
-    uint32_t item_pos;   // first of the tile's queries in the list-sorted item array
-    uint32_t nq;         // 1..TRI_QT real queries
-    uint32_t pad_;
-    uint64_t score_off;  // element offset of query 0's score segment; query j at + j*npad
+    uint64_t vec_addr;    // device address of the chunk's first vector
+    uint64_t vnorm_addr;  // device address of the chunk's first |x|^2
+    uint64_t score_off;   // element offset of the score of (query 0, first vector of the chunk); query j at + j*npad
+    uint32_t item_pos;    // first of the tile's queries in the list-sorted item array
+    uint32_t nq;          // 1..TRI_QT real queries
+    uint32_t vec_count;   // vectors in the chunk
+    uint32_t npad;        // padded list length = score pitch between queries
+    uint32_t klass;       // which scan kernel serves it (tri_scan_class)
+    uint32_t row_bytes;
+    uint32_t pad_[2];
 };
 
 // Small per-step numbers the device produces for the host (copied back with the results).
@@ -84,6 +91,7 @@ struct TriDevWs {
     uint32_t *glist_len;      // [max_total_lists]
     uint32_t *glist_voff;     // [max_total_lists] first stored position inside its index
     uint32_t *glist_index;    // [max_total_lists]
+    uint32_t *glist_order;    // [max_total_lists] attached lists by descending byte length (scan order)
     // per-step upload block (device copy)
     uint8_t *upload;          // upload_bytes
     // coarse ranking
@@ -98,8 +106,8 @@ struct TriDevWs {
     uint32_t *list_start;     // [max_total_lists+1]
     uint32_t *tile_base;      // [max_total_lists+1]
     uint64_t *score_base;     // [max_total_lists+1]
-    TriTile *tiles;           // [W]
-    uint32_t *tile_counter;   // [1] work-queue head of the scan kernel
+    TriTile *tiles;           // [TRI_TILES_PER_ITEM * W]
+    uint32_t *tile_counter;   // [TRI_SCAN_CLASSES] work-queue heads of the scan kernels
     TriStepDev *step_dev;     // [1]
     float *scores;            // [score_capacity]
     // results of retiring slots, compact, per step
@@ -125,11 +133,19 @@ hipError_t tri_launch_coarse_gemm(hipStream_t s, int dtype, const void *a_rows, 
 hipError_t tri_launch_coarse_select(const TriLaunchCtx &c, const TriDevWs &ws, const TriNewDesc *desc_dev,
                                     uint32_t first_new, uint32_t m, uint32_t nlist, uint32_t ldc);
 hipError_t tri_launch_pack(const TriLaunchCtx &c, const TriDevWs &ws, const TriPlanEntry *plan_dev,
-                           uint32_t n_plan, uint32_t n_items, uint32_t total_lists);
-hipError_t tri_launch_scan(const TriLaunchCtx &c, const TriDevWs &ws, uint32_t max_row_bytes);
+                           uint32_t n_plan, uint32_t n_items, uint32_t total_lists, uint32_t n_order,
+                           uint32_t chunk_vecs);
+hipError_t tri_launch_scan(const TriLaunchCtx &c, const TriDevWs &ws, uint32_t max_row_bytes, uint32_t class_mask);
+#define TRI_TILES_PER_ITEM 4   // tile capacity = 4 W: a list is cut into at most 4 chunks
+
+// Which scan kernel serves an index: 5 classes per storage type (other, 512, 1024, 1536, 2048 bytes per row).
+__host__ __device__ inline uint32_t tri_scan_class(uint32_t dtype, uint32_t row_bytes)
+{
+    const bool special = row_bytes == 512 || row_bytes == 1024 || row_bytes == 1536 || row_bytes == 2048;
+    return dtype * 5 + (special ? row_bytes / 512 : 0);
+}
 hipError_t tri_launch_merge(const TriLaunchCtx &c, const TriDevWs &ws, const TriPlanEntry *plan_dev,
                             uint32_t n_plan, bool keep_probes);
-hipError_t tri_scan_configure(uint32_t max_row_bytes);   // raises the scan kernel's dynamic-LDS limit
 
 // ---- index construction helpers ------------------------------------------------------------
 hipError_t tri_build_pad_rows(hipStream_t s, int dtype, const void *src, uint32_t dim, uint64_t src_pitch_elems,
