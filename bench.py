@@ -82,7 +82,7 @@ def main():
 
     pool = tri.Pool(slots=Q, items_per_step=items, lists_per_query_step=0, kmax=max(kmax, 16),
                     nprobe_max=int(nprobe.max()), max_indexes=1, max_total_lists=cfg.nlist, max_nlist=cfg.nlist,
-                    max_dim=cfg.dim, max_outstanding=Q * 8, coarse_rows=0, flags=tri.TRI_FLAG_PROFILE,
+                    max_dim=cfg.dim, max_outstanding=Q * 8, coarse_rows=Q, flags=tri.TRI_FLAG_PROFILE,
                     score_capacity=(1 << 30))
     log("building the index (untimed)")
     t_b = time.time()

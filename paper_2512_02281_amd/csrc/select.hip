@@ -1,5 +1,4 @@
-// Per-query top-k: a workgroup-level radix select over fp32 scores followed by a bitonic sort of
-// the k survivors (the paper's Sec. 3.2 step "scatter (id, dist) back to the owning request and
+// Per-query top-k (the paper's Sec. 3.2 step "scatter (id, dist) back to the owning request and
 // merge into its topM"; here the request's candidates of one step are the score segments of its
 // work items plus its running top-k).
 //
@@ -8,12 +7,23 @@
 // therefore ordered by ascending id, which makes the result independent of how the candidates
 // were batched.
 //
-// Selection: three histogram passes (11 + 11 + 10 bits) find the key T of the k-th best element;
-// if more elements equal T than are still needed, three more passes over the ids of those
-// elements find the largest id to keep; one collect pass gathers exactly k pairs.
+// One workgroup selects for one query, in LDS:
+//  (1) at most SEL_CAP candidates: all (key, id) pairs are loaded and sorted (bitonic network).
+//  (2) more: a strided sample of about SEL_SAMPLE keys is sorted; the sample's m-th key, with m
+//      five standard deviations above the expected rank of the k-th best, is a threshold that almost
+//      surely admits at least k and far fewer than SEL_CAP candidates; ONE pass over the candidates
+//      collects those not worse than it, and they are sorted as in (1).  Whatever the sample says,
+//      the result is exact whenever the pass collected between k and SEL_CAP candidates: the k best
+//      of the collected set are then the k best of all.
+//  (3) otherwise (heavy ties, adversarial order): three histogram passes (11 + 11 + 10 bits) find
+//      the key T of the k-th best element; if more elements equal T than are still needed, three more
+//      passes over the ids of those elements find the largest id to keep; one pass gathers exactly k.
 #include "tri_common.h"
 
 #define SEL_BINS 2048
+#define SEL_SEGCACHE 256   // segment descriptors cached in LDS
+#define SEL_CAP 4096      // (key, id) pairs sorted in LDS
+#define SEL_SAMPLE 1024   // target size of the key sample (at most SEL_CAP keys are kept)
 
 __device__ __forceinline__ uint32_t sel_key(float f, uint32_t desc)
 {
@@ -39,11 +49,14 @@ struct SelSeg {
 };
 
 struct SelShared {
+    uint64_t pool[SEL_CAP];        // candidates / result (the sample's keys use its first half as uint32_t[SEL_CAP])
     uint32_t hist[SEL_BINS];
-    uint64_t out[TRI_KMAX_POW2];
+    SelSeg seg[SEL_SEGCACHE];      // descriptors of the first segments
     uint32_t wave_tot[8];
     uint32_t digit, need, count, cnt;
 };
+
+__device__ __forceinline__ uint32_t sel_id(const SelSeg &sg, uint32_t i) { return sg.ids ? sg.ids[i] : sg.id_base + i; }
 
 // Inclusive scan of one value per thread across the workgroup (TRI_SEL_THREADS threads).
 __device__ __forceinline__ uint32_t sel_block_scan_incl(uint32_t v, uint32_t *wave_tot)
@@ -89,84 +102,71 @@ __device__ __forceinline__ void sel_find_digit(SelShared &sh, uint32_t nbins, ui
     __syncthreads();
 }
 
-// Enumerate every candidate: f(key, seg, pos).  Wavefronts take segments round-robin.
+// Enumerate candidates with wavefront-uniform control flow: f(valid, key, seg, pos) is called by all
+// 64 lanes together (valid = this lane has an element).  The segments are cut into chunks of
+// 64 * SEL_UNROLL elements and the workgroup's wavefronts take chunks round-robin across ALL
+// segments, so one long segment keeps every wavefront busy and many short ones are spread evenly;
+// the SEL_UNROLL loads of a chunk are issued together.  `stride` > 1 visits only the first
+// ceil(len / stride) elements of every segment (the sample: list order is id order, which carries no
+// information about the scores).  Segment descriptors come from the LDS cache filled by
+// sel_cache_segments, beyond it from seg_of.
+#define SEL_UNROLL 8
+
 template <class SegFn, class Fn>
-__device__ __forceinline__ void sel_for_each(uint32_t nseg, SegFn seg_of, uint32_t desc, Fn f)
+__device__ __forceinline__ void sel_for_each(const SelSeg *cache, uint32_t nseg, SegFn seg_of, uint32_t desc,
+                                             uint32_t stride, Fn f)
 {
     const uint32_t lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    for (uint32_t s = wave; s < nseg; s += TRI_SEL_THREADS / 64) {
-        const SelSeg sg = seg_of(s);
-        for (uint32_t i = lane; i < sg.len; i += 64) f(sel_key(sg.scores[i], desc), sg, i);
+    constexpr uint32_t CH = 64 * SEL_UNROLL;
+    uint32_t next = wave, base = 0;
+    for (uint32_t s = 0; s < nseg; ++s) {
+        const SelSeg sg = s < SEL_SEGCACHE ? cache[s] : seg_of(s);
+        const uint32_t n = stride > 1 ? (sg.len + stride - 1) / stride : sg.len;
+        const uint32_t nch = (n + CH - 1) / CH;
+        while (next < base + nch) {
+            const uint32_t i0 = (next - base) * CH + lane;
+            float v[SEL_UNROLL];
+#pragma unroll
+            for (int u = 0; u < SEL_UNROLL; ++u) v[u] = i0 + u * 64 < n ? sg.scores[i0 + u * 64] : 0.f;
+#pragma unroll
+            for (int u = 0; u < SEL_UNROLL; ++u) {
+                const bool valid = i0 + u * 64 < n;
+                f(valid, valid ? sel_key(v[u], desc) : 0xFFFFFFFFu, sg, i0 + u * 64);
+            }
+            next += TRI_SEL_THREADS / 64;
+        }
+        base += nch;
     }
 }
 
-// Select the k best of `total` candidates into sh.out[0..n) sorted ascending by (key, id).
-// Returns n = min(k, total).  All threads of the workgroup must call it.
 template <class SegFn>
-__device__ uint32_t sel_block_topk(SelShared &sh, uint32_t nseg, SegFn seg_of, uint32_t total, uint32_t k,
-                                   uint32_t desc)
+__device__ __forceinline__ void sel_cache_segments(SelSeg *cache, uint32_t nseg, SegFn seg_of)
+{
+    for (uint32_t s = threadIdx.x; s < nseg && s < SEL_SEGCACHE; s += TRI_SEL_THREADS) cache[s] = seg_of(s);
+    __syncthreads();
+}
+
+// Append slot for every lane with pred set: one LDS atomic per wavefront call, not per lane.
+__device__ __forceinline__ uint32_t sel_append_pos(bool pred, uint32_t *counter)
+{
+    const uint64_t m = __ballot(pred);
+    if (m == 0) return 0;
+    const uint32_t lane = threadIdx.x & 63;
+    const int leader = __ffsll((unsigned long long)m) - 1;
+    uint32_t base = 0;
+    if ((int)lane == leader) base = atomicAdd(counter, (uint32_t)__popcll(m));
+    base = __shfl(base, leader, 64);
+    return base + (uint32_t)__popcll(m & ((1ull << lane) - 1ull));
+}
+
+// Bitonic sort (ascending) of n elements of LDS array a, padded with all-ones up to a power of two.
+template <typename T>
+__device__ __forceinline__ void sel_bitonic(T *a, uint32_t n)
 {
     const uint32_t tid = threadIdx.x;
-    uint32_t T = 0xFFFFFFFFu, Tid = 0xFFFFFFFFu;
-    const uint32_t n = total < k ? total : k;
-    if (total > k) {
-        // ---- key of the k-th best element
-        uint32_t need = k, prefix = 0;
-        const uint32_t shifts[3] = {21, 10, 0}, widths[3] = {11, 11, 10};
-        uint32_t count_eq = 0;
-        for (int pass = 0; pass < 3; ++pass) {
-            const uint32_t shift = shifts[pass], width = widths[pass], nb = 1u << width;
-            for (uint32_t i = tid; i < SEL_BINS; i += TRI_SEL_THREADS) sh.hist[i] = 0;
-            __syncthreads();
-            const uint32_t hi_shift = shift + width;
-            sel_for_each(nseg, seg_of, desc, [&](uint32_t key, const SelSeg &, uint32_t) {
-                if (pass == 0 || (key >> hi_shift) == prefix) atomicAdd(&sh.hist[(key >> shift) & (nb - 1)], 1u);
-            });
-            __syncthreads();
-            sel_find_digit(sh, nb, need);
-            prefix = (prefix << width) | sh.digit;
-            need = sh.need;
-            count_eq = sh.count;
-            __syncthreads();
-        }
-        T = prefix;
-        // ---- ties at T: keep the `need` smallest ids among the count_eq elements equal to T
-        if (need < count_eq) {
-            uint32_t idprefix = 0, need_id = need;
-            for (int pass = 0; pass < 3; ++pass) {
-                const uint32_t shift = shifts[pass], width = widths[pass], nb = 1u << width;
-                for (uint32_t i = tid; i < SEL_BINS; i += TRI_SEL_THREADS) sh.hist[i] = 0;
-                __syncthreads();
-                const uint32_t hi_shift = shift + width;
-                sel_for_each(nseg, seg_of, desc, [&](uint32_t key, const SelSeg &sg, uint32_t i) {
-                    if (key != T) return;
-                    const uint32_t id = sg.ids ? sg.ids[i] : sg.id_base + i;
-                    if (pass == 0 || (id >> hi_shift) == idprefix) atomicAdd(&sh.hist[(id >> shift) & (nb - 1)], 1u);
-                });
-                __syncthreads();
-                sel_find_digit(sh, nb, need_id);
-                idprefix = (idprefix << width) | sh.digit;
-                need_id = sh.need;
-                __syncthreads();
-            }
-            Tid = idprefix;
-        }
-    }
-    // ---- collect
-    if (tid == 0) sh.cnt = 0;
-    __syncthreads();
-    sel_for_each(nseg, seg_of, desc, [&](uint32_t key, const SelSeg &sg, uint32_t i) {
-        if (key > T) return;
-        const uint32_t id = sg.ids ? sg.ids[i] : sg.id_base + i;
-        if (key == T && id > Tid) return;
-        const uint32_t pos = atomicAdd(&sh.cnt, 1u);
-        if (pos < TRI_KMAX_POW2) sh.out[pos] = ((uint64_t)key << 32) | id;
-    });
-    __syncthreads();
-    // ---- sort the survivors (bitonic, padded with the largest composite)
     uint32_t np2 = 1;
     while (np2 < n) np2 <<= 1;
-    for (uint32_t i = n + tid; i < np2; i += TRI_SEL_THREADS) sh.out[i] = ~0ull;
+    for (uint32_t i = n + tid; i < np2; i += TRI_SEL_THREADS) a[i] = (T)~(T)0;
     __syncthreads();
     for (uint32_t size = 2; size <= np2; size <<= 1) {
         for (uint32_t stride = size >> 1; stride > 0; stride >>= 1) {
@@ -174,14 +174,136 @@ __device__ uint32_t sel_block_topk(SelShared &sh, uint32_t nseg, SegFn seg_of, u
                 const uint32_t lo = 2 * i - (i & (stride - 1));   // index with the `stride` bit clear
                 const uint32_t hi = lo + stride;
                 const bool up = (lo & size) == 0;
-                const uint64_t a = sh.out[lo], b = sh.out[hi];
-                if ((a > b) == up) {
-                    sh.out[lo] = b;
-                    sh.out[hi] = a;
+                const T x = a[lo], y = a[hi];
+                if ((x > y) == up) {
+                    a[lo] = y;
+                    a[hi] = x;
                 }
             }
             __syncthreads();
         }
+    }
+}
+
+// Path (3): exact radix select of the k best into sh.pool[0..k), unsorted.  total > k.
+template <class SegFn>
+__device__ void sel_radix(SelShared &sh, uint32_t nseg, SegFn seg_of, uint32_t k, uint32_t desc)
+{
+    const uint32_t tid = threadIdx.x;
+    uint32_t T = 0, Tid = 0xFFFFFFFFu;
+    uint32_t need = k, prefix = 0, count_eq = 0;
+    const uint32_t shifts[3] = {21, 10, 0}, widths[3] = {11, 11, 10};
+    for (int pass = 0; pass < 3; ++pass) {
+        const uint32_t shift = shifts[pass], width = widths[pass], nb = 1u << width;
+        for (uint32_t i = tid; i < SEL_BINS; i += TRI_SEL_THREADS) sh.hist[i] = 0;
+        __syncthreads();
+        const uint32_t hi_shift = shift + width;
+        sel_for_each(sh.seg, nseg, seg_of, desc, 1u, [&](bool valid, uint32_t key, const SelSeg &, uint32_t) {
+            if (valid && (pass == 0 || (key >> hi_shift) == prefix)) atomicAdd(&sh.hist[(key >> shift) & (nb - 1)], 1u);
+        });
+        __syncthreads();
+        sel_find_digit(sh, nb, need);
+        prefix = (prefix << width) | sh.digit;
+        need = sh.need;
+        count_eq = sh.count;
+        __syncthreads();
+    }
+    T = prefix;
+    // ties at T: keep the `need` smallest ids among the count_eq elements equal to T
+    if (need < count_eq) {
+        uint32_t idprefix = 0, need_id = need;
+        for (int pass = 0; pass < 3; ++pass) {
+            const uint32_t shift = shifts[pass], width = widths[pass], nb = 1u << width;
+            for (uint32_t i = tid; i < SEL_BINS; i += TRI_SEL_THREADS) sh.hist[i] = 0;
+            __syncthreads();
+            const uint32_t hi_shift = shift + width;
+            sel_for_each(sh.seg, nseg, seg_of, desc, 1u, [&](bool valid, uint32_t key, const SelSeg &sg, uint32_t i) {
+                if (!valid || key != T) return;
+                const uint32_t id = sel_id(sg, i);
+                if (pass == 0 || (id >> hi_shift) == idprefix) atomicAdd(&sh.hist[(id >> shift) & (nb - 1)], 1u);
+            });
+            __syncthreads();
+            sel_find_digit(sh, nb, need_id);
+            idprefix = (idprefix << width) | sh.digit;
+            need_id = sh.need;
+            __syncthreads();
+        }
+        Tid = idprefix;
+    }
+    if (tid == 0) sh.cnt = 0;
+    __syncthreads();
+    sel_for_each(sh.seg, nseg, seg_of, desc, 1u, [&](bool valid, uint32_t key, const SelSeg &sg, uint32_t i) {
+        bool take = valid && key <= T;
+        uint32_t id = 0;
+        if (take) {
+            id = sel_id(sg, i);
+            take = key < T || id <= Tid;
+        }
+        const uint32_t pos = sel_append_pos(take, &sh.cnt);
+        if (take && pos < SEL_CAP) sh.pool[pos] = ((uint64_t)key << 32) | id;
+    });
+    __syncthreads();
+}
+
+// Select the k best of `total` candidates into sh.pool[0..n) sorted ascending by (key, id).
+// Returns n = min(k, total).  All threads of the workgroup must call it; it ends with a barrier.
+template <class SegFn>
+__device__ uint32_t sel_block_topk(SelShared &sh, uint32_t nseg, SegFn seg_of, uint32_t total, uint32_t k,
+                                   uint32_t desc)
+{
+    const uint32_t tid = threadIdx.x;
+    const uint32_t n = total < k ? total : k;
+    sel_cache_segments(sh.seg, nseg, seg_of);
+    if (total <= SEL_CAP) {
+        // ---- (1) everything fits
+        if (tid == 0) sh.cnt = 0;
+        __syncthreads();
+        sel_for_each(sh.seg, nseg, seg_of, desc, 1u, [&](bool valid, uint32_t key, const SelSeg &sg, uint32_t i) {
+            const uint32_t pos = sel_append_pos(valid, &sh.cnt);
+            if (valid) sh.pool[pos] = ((uint64_t)key << 32) | sel_id(sg, i);
+        });
+        __syncthreads();
+        sel_bitonic(sh.pool, total);
+        return n;
+    }
+    // ---- (2) threshold from a sorted sample
+    uint32_t *skeys = (uint32_t *)sh.pool;
+    const uint32_t stride = (total + SEL_SAMPLE - 1) / SEL_SAMPLE;
+    if (tid == 0) sh.cnt = 0;
+    __syncthreads();
+    sel_for_each(sh.seg, nseg, seg_of, desc, stride, [&](bool valid, uint32_t key, const SelSeg &, uint32_t) {
+        const uint32_t pos = sel_append_pos(valid, &sh.cnt);
+        if (valid && pos < SEL_CAP) skeys[pos] = key;      // (a few sample keys too many are simply dropped)
+    });
+    __syncthreads();
+    const uint32_t ns = sh.cnt < SEL_CAP ? sh.cnt : SEL_CAP;
+    sel_bitonic(skeys, ns);
+    // expected rank of the k-th best inside the sample, plus five standard deviations and a floor
+    const float mu = (float)k * (float)ns / (float)total;
+    const uint32_t m = (uint32_t)(mu + 5.0f * sqrtf(mu) + 4.0f);
+    bool done = false;
+    if (m < ns) {
+        const uint32_t t0 = skeys[m];
+        __syncthreads();                       // everyone has read the threshold before the pool is reused
+        if (tid == 0) sh.cnt = 0;
+        __syncthreads();
+        sel_for_each(sh.seg, nseg, seg_of, desc, 1u, [&](bool valid, uint32_t key, const SelSeg &sg, uint32_t i) {
+            const bool take = valid && key <= t0;
+            const uint32_t pos = sel_append_pos(take, &sh.cnt);
+            if (take && pos < SEL_CAP) sh.pool[pos] = ((uint64_t)key << 32) | sel_id(sg, i);
+        });
+        __syncthreads();
+        const uint32_t c = sh.cnt;
+        if (c >= k && c <= SEL_CAP) {
+            sel_bitonic(sh.pool, c);
+            done = true;
+        }
+    }
+    __syncthreads();
+    if (!done) {
+        // ---- (3) exact radix select, then sort the k survivors
+        sel_radix(sh, nseg, seg_of, k, desc);
+        sel_bitonic(sh.pool, k);
     }
     return n;
 }
@@ -199,7 +321,7 @@ __global__ __launch_bounds__(TRI_SEL_THREADS) void coarse_select_kernel(
     auto seg_of = [&](uint32_t) { return SelSeg{row, nullptr, nlist, 0u}; };
     const uint32_t n = sel_block_topk(sh, 1u, seg_of, nlist, d.nprobe, d.metric);
     uint32_t *dst = probe + (size_t)d.slot * nprobe_max;
-    for (uint32_t i = threadIdx.x; i < n; i += TRI_SEL_THREADS) dst[i] = (uint32_t)(sh.out[i] & 0xFFFFFFFFu);
+    for (uint32_t i = threadIdx.x; i < n; i += TRI_SEL_THREADS) dst[i] = (uint32_t)(sh.pool[i] & 0xFFFFFFFFu);
 }
 
 hipError_t tri_launch_coarse_select(const TriLaunchCtx &c, const TriDevWs &ws, const TriNewDesc *desc_dev,
@@ -258,7 +380,7 @@ __global__ __launch_bounds__(TRI_SEL_THREADS) void slot_merge_kernel(
         uint32_t *rec = res_block + (size_t)e.retire_idx * (1u + 2u * kmax);
         if (threadIdx.x == 0) rec[0] = n;
         for (uint32_t i = threadIdx.x; i < n; i += TRI_SEL_THREADS) {
-            const uint64_t c = sh.out[i];
+            const uint64_t c = sh.pool[i];
             rec[1 + i] = (uint32_t)(c & 0xFFFFFFFFu);
             rec[1 + kmax + i] = __float_as_uint(sel_unkey((uint32_t)(c >> 32), desc));
         }
@@ -269,7 +391,7 @@ __global__ __launch_bounds__(TRI_SEL_THREADS) void slot_merge_kernel(
         }
     } else {
         for (uint32_t i = threadIdx.x; i < n; i += TRI_SEL_THREADS) {
-            const uint64_t c = sh.out[i];
+            const uint64_t c = sh.pool[i];
             run_id[i] = (uint32_t)(c & 0xFFFFFFFFu);
             run_score[i] = sel_unkey((uint32_t)(c >> 32), desc);
         }

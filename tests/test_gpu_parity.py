@@ -368,3 +368,23 @@ def test_config4_full_size_in_the_benchmark_configuration():
             assert np.all(np.abs(dist[i] - want) <= 2e-3 * np.abs(want) + checker.ABS_EPS)
     finally:
         pool.close()
+
+
+def test_massive_ties_take_the_exact_path():
+    """Thousands of identical vectors: far more candidates tie at the k-th score than fit the sorted
+    pool, so selection must fall back to the exact radix path and still order ties by id."""
+    tri = harness.lib()
+    rng = np.random.default_rng(21)
+    protos = rng.integers(-3, 4, size=(3, 16)).astype(np.float32)
+    base = protos[rng.integers(0, 3, size=30_000)]
+    cent = np.stack([protos[0], protos[1], protos[2], protos[0] + 0.5]).astype(np.float32)
+    queries = (protos[rng.integers(0, 3, size=12)] + 0.25).astype(np.float32)
+    with harness.default_pool(tri, max_dim=16, kmax=1024, max_nlist=8, max_total_lists=8, score_capacity=1 << 20) as pool:
+        idx = pool.build_index(base, 16, 4, tri.TRI_F32, tri.TRI_L2, 0, centroids=cent)
+        oidx = harness.oracle_index(tri, idx, base)
+        for k, nprobe, metric in [(100, 4, 0), (1024, 2, 0), (7, 4, 1), (1000, 4, 1)]:
+            _say(f"ties: k={k} nprobe={nprobe} metric={metric}")
+            q = tri.make_queries(idx, queries, k, nprobe, metric)
+            ids, dist, n_out, probes, _ = harness.run_all(tri, pool, q)
+            # integer-valued data + quarter offsets: every score is exact in fp32 -> strict comparison
+            harness.compare_with_oracle(oidx, base, queries, k, nprobe, metric, ids, dist, n_out, probes, strict=True)
