@@ -83,7 +83,7 @@ def main():
     pool = tri.Pool(slots=Q, items_per_step=items, lists_per_query_step=0, kmax=max(kmax, 16),
                     nprobe_max=int(nprobe.max()), max_indexes=1, max_total_lists=cfg.nlist, max_nlist=cfg.nlist,
                     max_dim=cfg.dim, max_outstanding=Q * 8, coarse_rows=Q, flags=tri.TRI_FLAG_PROFILE,
-                    score_capacity=(1 << 30))
+                    score_capacity=(1 << 31))
     log("building the index (untimed)")
     t_b = time.time()
     init = base_t[torch.from_numpy(rows).cuda()].float().cpu().numpy()
@@ -154,7 +154,7 @@ def main():
     achieved = unique_b / (scan_ms * 1e-3) / 1e9 if scan_ms > 0 else 0.0
     log(f"{ms_per_step:.3f} ms/step, {qps:.0f} q/s; scan {scan_ms:.3f} ms/launch, unique {unique_b / 1e9:.2f} GB "
         f"-> {achieved:.0f} GB/s; stages ms/step: admit {kt.admit_ms / kt.steps:.3f} coarse {kt.coarse_ms / kt.steps:.3f} "
-        f"pack {kt.pack_ms / kt.steps:.3f} scan {kt.scan_ms / kt.steps:.3f} select {kt.select_ms / kt.steps:.3f}")
+        f"pack {kt.pack_ms / kt.steps:.3f} sample {kt.sample_ms / kt.steps:.3f} scan {kt.scan_ms / kt.steps:.3f} select {kt.select_ms / kt.steps:.3f}")
 
     # ---- recall of the returned lists against exact search (torch matmul on the GPU, harness only)
     recall = None
@@ -211,7 +211,8 @@ def main():
                      "algorithmic_bytes_per_launch": int(unique_b), "tile_bytes_per_launch": int(tile_b),
                      "items_per_launch": int(kt.scan_items / max(kt.scan_launches, 1)), "row_bytes": row_bytes},
         "stages_ms_per_step": {"admit": round(kt.admit_ms / kt.steps, 4), "coarse": round(kt.coarse_ms / kt.steps, 4),
-                               "pack": round(kt.pack_ms / kt.steps, 4), "scan": round(kt.scan_ms / kt.steps, 4),
+                               "pack": round(kt.pack_ms / kt.steps, 4), "sample": round(kt.sample_ms / kt.steps, 4),
+                               "scan": round(kt.scan_ms / kt.steps, 4),
                                "select": round(kt.select_ms / kt.steps, 4)},
         "cpu_baseline": cpu,
         "wall_s_total": round(time.time() - t_start, 1),

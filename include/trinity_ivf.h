@@ -71,7 +71,7 @@ typedef struct {
     uint32_t max_outstanding;      /* tickets alive at once (pending + running + finished, not yet polled)  */
     uint32_t coarse_rows;          /* new queries ranked against centroids per launch (0 = default 1024)    */
     uint32_t flags;                /* TRI_FLAG_*                                                           */
-    uint64_t score_capacity;       /* candidate scores one step may produce (elements, 4 B each); 0 = W*1024 */
+    uint64_t score_capacity;       /* 4-byte words of the step's candidate buffer (2 per scanned vector and query); 0 = W*2048 */
     void *hip_stream;              /* hipStream_t all work is enqueued on (NULL = the null stream)          */
 } tri_pool_cfg;
 
@@ -215,6 +215,7 @@ typedef struct {
     double admit_ms;         /* query rows into slots                                              */
     double coarse_ms;        /* centroid contraction + top-nprobe selection                        */
     double pack_ms;          /* work-item array and tile table                                     */
+    double sample_ms;        /* sample scan + per-query thresholds                                  */
     double scan_ms;          /* list scan                                                          */
     double select_ms;        /* per-query top-k merge, result copy-out enqueue                     */
     uint64_t scan_launches;  /* list-scan kernel launches                                          */

@@ -119,16 +119,17 @@ __global__ __launch_bounds__(1024) void pack_scan_kernel(const uint32_t *__restr
                                                          const TriIndexDev *__restrict__ indexes,
                                                          uint32_t *__restrict__ list_start,
                                                          uint32_t *__restrict__ tile_base,
+                                                         uint32_t *__restrict__ stile_base,
                                                          uint64_t *__restrict__ score_base,
                                                          TriStepDev *__restrict__ step_dev,
                                                          uint32_t *__restrict__ tile_counter, uint32_t chunk_vecs)
 {
-    __shared__ uint32_t s_items[1024], s_tiles[1024], s_lists[1024];
+    __shared__ uint32_t s_items[1024], s_tiles[1024], s_lists[1024], s_stiles[1024];
     __shared__ uint64_t s_scores[1024], s_tbytes[1024], s_ubytes[1024];
     const uint32_t t = threadIdx.x;
     const uint32_t per = (n_order + 1023) / 1024;
     const uint32_t i0 = min(t * per, n_order), i1 = min(i0 + per, n_order);
-    uint32_t items = 0, tiles = 0, lists = 0;
+    uint32_t items = 0, tiles = 0, lists = 0, stiles = 0;
     uint64_t sc = 0, tb = 0, ub = 0;
     for (uint32_t i = i0; i < i1; ++i) {
         const uint32_t g = glist_order[i];
@@ -139,50 +140,54 @@ __global__ __launch_bounds__(1024) void pack_scan_kernel(const uint32_t *__restr
             const uint64_t bytes = (uint64_t)len * indexes[glist_index[g]].row_bytes;
             items += c;
             tiles += nt * ((len + chunk_vecs - 1) / chunk_vecs);
+            stiles += len ? nt : 0;
             lists += 1;
-            sc += (uint64_t)c * ((len + TRI_VB - 1) / TRI_VB * TRI_VB);
+            sc += (uint64_t)c * 2u * ((len + TRI_VB - 1) / TRI_VB * TRI_VB);
             tb += bytes * nt;
             ub += bytes;
         }
     }
-    s_items[t] = items; s_tiles[t] = tiles; s_lists[t] = lists;
+    s_items[t] = items; s_tiles[t] = tiles; s_lists[t] = lists; s_stiles[t] = stiles;
     s_scores[t] = sc; s_tbytes[t] = tb; s_ubytes[t] = ub;
     __syncthreads();
     // Hillis-Steele inclusive scan over the 1024 thread totals
     for (uint32_t d = 1; d < 1024; d <<= 1) {
-        uint32_t a = 0, b = 0, l = 0;
+        uint32_t a = 0, b = 0, l = 0, e = 0;
         uint64_t x = 0, y = 0, z = 0;
         if (t >= d) {
-            a = s_items[t - d]; b = s_tiles[t - d]; l = s_lists[t - d];
+            a = s_items[t - d]; b = s_tiles[t - d]; l = s_lists[t - d]; e = s_stiles[t - d];
             x = s_scores[t - d]; y = s_tbytes[t - d]; z = s_ubytes[t - d];
         }
         __syncthreads();
-        s_items[t] += a; s_tiles[t] += b; s_lists[t] += l;
+        s_items[t] += a; s_tiles[t] += b; s_lists[t] += l; s_stiles[t] += e;
         s_scores[t] += x; s_tbytes[t] += y; s_ubytes[t] += z;
         __syncthreads();
     }
-    uint32_t it = s_items[t] - items, ti = s_tiles[t] - tiles;
+    uint32_t it = s_items[t] - items, ti = s_tiles[t] - tiles, sti = s_stiles[t] - stiles;
     uint64_t so = s_scores[t] - sc;
     for (uint32_t i = i0; i < i1; ++i) {
         const uint32_t g = glist_order[i];
         const uint32_t c = hist[g];
         list_start[g] = it;
         tile_base[g] = ti;
+        stile_base[g] = sti;
         score_base[g] = so;
         if (c) {
             const uint32_t len = glist_len[g];
             it += c;
             ti += (c + TRI_QT - 1) / TRI_QT * ((len + chunk_vecs - 1) / chunk_vecs);
-            so += (uint64_t)c * ((len + TRI_VB - 1) / TRI_VB * TRI_VB);
+            sti += len ? (c + TRI_QT - 1) / TRI_QT : 0;
+            so += (uint64_t)c * 2u * ((len + TRI_VB - 1) / TRI_VB * TRI_VB);
         }
     }
     if (t == 1023) {
         step_dev->n_tiles = s_tiles[t];
+        step_dev->n_sample_tiles = s_stiles[t];
         step_dev->n_lists_touched = s_lists[t];
         step_dev->total_scores = s_scores[t];
         step_dev->tile_vec_bytes = s_tbytes[t];
         step_dev->unique_vec_bytes = s_ubytes[t];
-        for (uint32_t k = 0; k < TRI_SCAN_CLASSES; ++k) tile_counter[k] = 0;
+        for (uint32_t k = 0; k < 2 * TRI_SCAN_CLASSES; ++k) tile_counter[k] = 0;
     }
 }
 
@@ -191,24 +196,26 @@ __global__ void pack_scatter_kernel(uint32_t n_items, const uint32_t *__restrict
                                     const uint32_t *__restrict__ item_slot, const uint32_t *__restrict__ item_rank,
                                     const uint32_t *__restrict__ list_start, const uint64_t *__restrict__ score_base,
                                     const uint32_t *__restrict__ glist_len, uint32_t *__restrict__ sorted_slot,
-                                    uint64_t *__restrict__ item_score_off)
+                                    uint64_t *__restrict__ item_score_off, uint32_t *__restrict__ item_sorted_pos)
 {
     const uint32_t i = blockIdx.x * blockDim.x + threadIdx.x;
     if (i >= n_items) return;
     const uint32_t g = item_glist[i], r = item_rank[i];
     const uint32_t npad = (glist_len[g] + TRI_VB - 1) / TRI_VB * TRI_VB;
     sorted_slot[list_start[g] + r] = item_slot[i];
-    item_score_off[i] = score_base[g] + (uint64_t)r * npad;
+    item_sorted_pos[i] = list_start[g] + r;
+    item_score_off[i] = score_base[g] + (uint64_t)r * 2u * npad;
 }
 
 // (4) tiles: one thread per list of the pool-wide table.  A list longer than chunk_vecs is cut into
-//     chunks; the tiles of one chunk (one per group of TRI_QT queries) are adjacent in the queue.
+//     chunks; the tiles of one chunk (one per group of TRI_QT queries) are adjacent in the queue.  Every
+//     list also gets its sample tiles (first TRI_SAMPLE_VECS vectors, one per group of queries).
 __global__ void pack_tiles_kernel(uint32_t total_lists, const uint32_t *__restrict__ hist,
                                   const uint32_t *__restrict__ list_start, const uint32_t *__restrict__ tile_base,
-                                  const uint64_t *__restrict__ score_base, const uint32_t *__restrict__ glist_len,
-                                  const uint32_t *__restrict__ glist_voff, const uint32_t *__restrict__ glist_index,
-                                  const TriIndexDev *__restrict__ indexes, uint32_t chunk_vecs,
-                                  TriTile *__restrict__ tiles)
+                                  const uint32_t *__restrict__ stile_base, const uint64_t *__restrict__ score_base,
+                                  const uint32_t *__restrict__ glist_len, const uint32_t *__restrict__ glist_voff,
+                                  const uint32_t *__restrict__ glist_index, const TriIndexDev *__restrict__ indexes,
+                                  uint32_t chunk_vecs, TriTile *__restrict__ tiles, TriTile *__restrict__ stiles)
 {
     const uint32_t g = blockIdx.x * blockDim.x + threadIdx.x;
     if (g >= total_lists) return;
@@ -220,23 +227,37 @@ __global__ void pack_tiles_kernel(uint32_t total_lists, const uint32_t *__restri
     const uint32_t nt = (c + TRI_QT - 1) / TRI_QT;
     const uint32_t nchunks = (len + chunk_vecs - 1) / chunk_vecs;
     const uint32_t voff = glist_voff[g];
+    TriTile tl;
+    tl.klass = tri_scan_class(ix.dtype, ix.row_bytes);
+    tl.row_bytes = ix.row_bytes;
     uint32_t w = tile_base[g];
     for (uint32_t ch = 0; ch < nchunks; ++ch) {
         const uint32_t v0 = ch * chunk_vecs;
+        tl.vec_addr = (uint64_t)(uintptr_t)ix.vecs + (uint64_t)(voff + v0) * ix.row_bytes;
+        tl.vnorm_addr = (uint64_t)(uintptr_t)(ix.vnorm + voff + v0);
+        tl.vec_count = min(chunk_vecs, len - v0);
+        tl.pitch = 2u * npad;
+        tl.vec_begin = v0;
+        tl.chunk = ch;
         for (uint32_t q = 0; q < nt; ++q) {
-            TriTile tl;
-            tl.vec_addr = (uint64_t)(uintptr_t)ix.vecs + (uint64_t)(voff + v0) * ix.row_bytes;
-            tl.vnorm_addr = (uint64_t)(uintptr_t)(ix.vnorm + voff + v0);
-            tl.score_off = score_base[g] + (uint64_t)q * TRI_QT * npad + v0;
+            tl.out_off = score_base[g] + (uint64_t)q * TRI_QT * 2u * npad + 2u * v0;
             tl.item_pos = list_start[g] + q * TRI_QT;
             tl.nq = min((uint32_t)TRI_QT, c - q * TRI_QT);
-            tl.vec_count = min(chunk_vecs, len - v0);
-            tl.npad = npad;
-            tl.klass = tri_scan_class(ix.dtype, ix.row_bytes);
-            tl.row_bytes = ix.row_bytes;
-            tl.pad_[0] = tl.pad_[1] = 0;
             tiles[w++] = tl;
         }
+    }
+    tl.vec_addr = (uint64_t)(uintptr_t)ix.vecs + (uint64_t)voff * ix.row_bytes;
+    tl.vnorm_addr = (uint64_t)(uintptr_t)(ix.vnorm + voff);
+    tl.vec_count = min((uint32_t)TRI_SAMPLE_VECS, len);
+    tl.pitch = TRI_SAMPLE_VECS;
+    tl.vec_begin = 0;
+    tl.chunk = 0;
+    w = stile_base[g];
+    for (uint32_t q = 0; q < nt; ++q) {
+        tl.item_pos = list_start[g] + q * TRI_QT;
+        tl.out_off = (uint64_t)tl.item_pos * TRI_SAMPLE_VECS;
+        tl.nq = min((uint32_t)TRI_QT, c - q * TRI_QT);
+        stiles[w++] = tl;
     }
 }
 
@@ -250,13 +271,13 @@ hipError_t tri_launch_pack(const TriLaunchCtx &c, const TriDevWs &ws, const TriP
                        n_items, ws.slot_meta, ws.indexes, ws.probe, c.nprobe_max, ws.item_glist, ws.item_slot,
                        ws.item_rank, ws.hist);
     hipLaunchKernelGGL(pack_scan_kernel, dim3(1), dim3(1024), 0, c.stream, ws.hist, n_order, ws.glist_order, ws.glist_len,
-                       ws.glist_index, ws.indexes, ws.list_start, ws.tile_base, ws.score_base, ws.step_dev,
-                       ws.tile_counter, chunk_vecs);
+                       ws.glist_index, ws.indexes, ws.list_start, ws.tile_base, ws.stile_base, ws.score_base,
+                       ws.step_dev, ws.tile_counter, chunk_vecs);
     hipLaunchKernelGGL(pack_scatter_kernel, dim3((n_items + 255) / 256), dim3(256), 0, c.stream, n_items,
                        ws.item_glist, ws.item_slot, ws.item_rank, ws.list_start, ws.score_base, ws.glist_len,
-                       ws.sorted_slot, ws.item_score_off);
+                       ws.sorted_slot, ws.item_score_off, ws.item_sorted_pos);
     hipLaunchKernelGGL(pack_tiles_kernel, dim3((total_lists + 255) / 256), dim3(256), 0, c.stream, total_lists,
-                       ws.hist, ws.list_start, ws.tile_base, ws.score_base, ws.glist_len, ws.glist_voff, ws.glist_index,
-                       ws.indexes, chunk_vecs, ws.tiles);
+                       ws.hist, ws.list_start, ws.tile_base, ws.stile_base, ws.score_base, ws.glist_len, ws.glist_voff,
+                       ws.glist_index, ws.indexes, chunk_vecs, ws.tiles, ws.stiles);
     return hipGetLastError();
 }

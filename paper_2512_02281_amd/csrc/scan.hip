@@ -11,13 +11,26 @@
 // Launch shape is fixed (a persistent grid that pulls tiles from a device-side queue); the number
 // of real tiles of the step is read from device memory, the rest of the capacity is padding.
 //
+// Output.  Writing every score would cost far more than its share of bytes (0.7 GB of stores beside
+// 15 GB of loads slowed the scan by a quarter), and almost all scores are useless: a query keeps k
+// of tens of thousands.  So each step runs the kernels twice:
+//  * sample launch (FILTER = false): the first TRI_SAMPLE_VECS vectors of every probed list, all
+//    scores written densely; a small kernel then sets each query's threshold to the k-th best of
+//    its sample (and running top-k).  A k-th best of a SUBSET of the candidates can only be worse
+//    than the k-th best of all of them, so nothing that belongs to the top-k is beyond it.
+//  * main launch (FILTER = true): every vector is scored, and only the scores not worse than the
+//    query's threshold are appended, as (score bits, position in list) pairs, to the (query, chunk)
+//    region of the candidate buffer.  The result is exact; the threshold only decides how much is
+//    written (about k / sample size of the scores).
+//
 // Two kernels:
 //  * scan_wave_kernel (rows of 512 / 1024 / 1536 bytes): ONE WAVEFRONT PER TILE, no LDS and no
 //    barriers.  The wavefront keeps the tile's 32 query rows in registers as MFMA operands (one
 //    wavefront per SIMD, so it owns all 512 vector registers) and streams the list through a
-//    register ring that holds one to three whole 32-vector blocks: while block b is multiplied,
-//    the 16-byte loads of block b + RB are in flight (about 48 KiB per wavefront).  Wavefronts are
-//    independent workers on the tile queue, so nothing waits at a barrier for a slower neighbour.
+//    register ring of RG 128-byte groups: while group g is multiplied, the 16-byte loads of the
+//    group RG steps ahead are in flight (16-24 KiB per wavefront, never drained at block or -- apart
+//    from the query load -- tile boundaries).  Wavefronts are independent workers on the tile queue,
+//    so nothing waits at a barrier for a slower neighbour.
 //  * scan_lds_kernel (any other row length): a workgroup of four wavefronts shares the tile's
 //    queries through LDS (row pitch = row bytes + 16: conflict-free 16-byte operand reads).
 //
@@ -73,20 +86,83 @@ __device__ __forceinline__ void scan_store_block(const tri_f32x16 &acc, float vn
     }
 }
 
+// Filtering epilogue of one 32-vector block: a score enters the candidate list of its query only if
+// its key is not above the query's threshold.  thr / cnt: LDS arrays indexed by the query's row in the
+// tile; a passing lane takes the next free pair of its query's region with an LDS atomic (the order
+// inside a region carries no meaning).
+typedef unsigned int scan_u32x2 __attribute__((ext_vector_type(2)));
+
+__device__ __forceinline__ void scan_filter_block(const tri_f32x16 &acc, float vn, const float (&qn)[16],
+                                                  uint32_t l2mask, const uint32_t *thr, uint32_t *cnt, uint32_t kg,
+                                                  uint32_t nq, bool vec_ok, uint32_t list_pos,
+                                                  __amdgpu_buffer_rsrc_t ors, uint32_t pitch_bytes)
+{
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+        const uint32_t j = 8 * (i / 4) + 4 * kg + (i % 4);
+        const bool is_l2 = (l2mask >> i) & 1u;
+        const float v = is_l2 ? (vn + qn[i]) - 2.0f * acc[i] : acc[i];
+        const uint32_t key = tri_score_key(v, is_l2 ? 0u : 1u);
+        if (vec_ok && j < nq && key <= thr[j]) {
+            const uint32_t pos = atomicAdd(&cnt[j], 1u);
+            const scan_u32x2 pair = {__float_as_uint(v), list_pos};
+            __builtin_amdgcn_raw_buffer_store_b64(pair, ors, j * pitch_bytes + pos * 8u, 0, 0);
+        }
+    }
+}
+
+// The same for the one-wavefront-per-tile kernel, without LDS round trips and without branches: the
+// running count of candidates of each of the lane's 16 queries lives in a register (identical in the 32
+// lanes of a half-wavefront, which share the query), a ballot gives each passing lane its place behind
+// it, and the 16 stores are issued unconditionally -- lanes that did not pass aim outside the buffer
+// descriptor and are dropped.  Straight-line code: the wavefront never waits for a store.
+__device__ __forceinline__ void scan_filter_block_reg(const tri_f32x16 &acc, float vn, const float (&qn)[16],
+                                                      uint32_t l2mask, const uint32_t (&thr)[16], uint32_t (&cnt)[16],
+                                                      uint32_t kg, uint32_t r, uint32_t nq, bool vec_ok,
+                                                      uint32_t list_pos, __amdgpu_buffer_rsrc_t ors,
+                                                      uint32_t pitch_bytes)
+{
+    float v[16];
+    uint32_t o[16];
+    const uint64_t below = (1ull << r) - 1ull;            // lanes of my half-wavefront before me
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+        const uint32_t j = 8 * (i / 4) + 4 * kg + (i % 4);
+        const bool is_l2 = (l2mask >> i) & 1u;
+        v[i] = is_l2 ? (vn + qn[i]) - 2.0f * acc[i] : acc[i];
+        const uint32_t key = tri_score_key(v[i], is_l2 ? 0u : 1u);
+        const bool pass = vec_ok && j < nq && key <= thr[i];
+        const uint64_t m = __ballot(pass);
+        const uint32_t half = kg ? (uint32_t)(m >> 32) : (uint32_t)m;
+        const uint32_t pos = cnt[i] + (uint32_t)__popc(half & (uint32_t)below);
+        o[i] = pass ? j * pitch_bytes + pos * 8u : 0xFFFFFFF8u;
+        cnt[i] += (uint32_t)__popc(half);
+    }
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+        const scan_u32x2 pair = {__float_as_uint(v[i]), list_pos};
+        __builtin_amdgcn_raw_buffer_store_b64(pair, ors, o[i], 0, 0);
+    }
+}
+
 // ================================================================================ wavefront kernel
-// NG = 128-byte groups per row, RB = 32-vector blocks held in the register ring.
-template <int DT, int NG, int RB>
+// NG = 128-byte groups per row, RG = groups held in the register ring (NG % RG == 0): while group g
+// of a block is multiplied, the loads of the group RG steps ahead -- in this block or the next --
+// are in flight.
+template <int DT, int NG, int RG, bool FILTER>
 __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(1, 1))) void scan_wave_kernel(
-    const TriTile *__restrict__ tiles, const TriStepDev *__restrict__ step_dev, uint32_t *__restrict__ tile_counter,
+    const TriTile *__restrict__ tiles, const uint32_t *__restrict__ n_tiles_ptr, uint32_t *__restrict__ tile_counter,
     uint32_t my_class, const uint32_t *__restrict__ sorted_slot, const uint8_t *__restrict__ slot_query,
     uint32_t slot_row_bytes, uint32_t n_slots, const TriSlotMeta *__restrict__ slot_meta,
-    const float *__restrict__ slot_qnorm, float *__restrict__ scores)
+    const float *__restrict__ slot_qnorm, const uint32_t *__restrict__ thr_key, uint32_t *__restrict__ surv_count,
+    float *__restrict__ out_buf)
 {
+    static_assert(NG % RG == 0, "ring slots must line up across blocks");
     constexpr uint32_t row_bytes = NG * 128;
     constexpr uint32_t blk_bytes = TRI_VB * row_bytes;
     const uint32_t lane = threadIdx.x;
     const uint32_t r = lane & 31, kg = lane >> 5;
-    const uint32_t n_tiles = step_dev->n_tiles;
+    const uint32_t n_tiles = *n_tiles_ptr;
     const __amdgpu_buffer_rsrc_t qrs =
         __builtin_amdgcn_make_buffer_rsrc((void *)slot_query, 0, n_slots * slot_row_bytes, SCAN_BUF_FLAGS);
 
@@ -105,17 +181,15 @@ __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(1, 1))) void
             // (sized to whole blocks: a 16-byte load never straddles its end; the norm array has a block of slack)
             const __amdgpu_buffer_rsrc_t nrs =
                 __builtin_amdgcn_make_buffer_rsrc((void *)tl.vnorm_addr, 0, nblocks * TRI_VB * 4u, SCAN_BUF_FLAGS);
-            // the stream's first RB blocks go out before anything else
-            const uint32_t off0 = r * row_bytes + kg * 16;
-            uint4 buf[RB][NG][4];
+            // the stream's first RG groups go out before anything else
+            uint32_t off = r * row_bytes + kg * 16;
+            uint4 buf[RG][4];
 #pragma unroll
-            for (int rb = 0; rb < RB; ++rb)
+            for (int g = 0; g < RG; ++g) {
 #pragma unroll
-                for (int g = 0; g < NG; ++g) {
-#pragma unroll
-                    for (int c = 0; c < 4; ++c) buf[rb][g][c] = scan_ld16(vrs, off0 + rb * blk_bytes + g * 128 + c * 32);
-                    __builtin_amdgcn_sched_barrier(0);
-                }
+                for (int c = 0; c < 4; ++c) buf[g][c] = scan_ld16(vrs, off + g * 128 + c * 32);
+                __builtin_amdgcn_sched_barrier(0);
+            }
             // this lane's query (row l%32 of the first MFMA operand): its vector as operand pieces; a
             // lane past nq reads out of range, i.e. zeros (masked padding).  All loads are issued
             // first; the empty asm statements then pin the pieces to accumulation registers, which
@@ -134,52 +208,66 @@ __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(1, 1))) void
             for (int g = 0; g < NG; ++g)
 #pragma unroll
                 for (int c = 0; c < 4; ++c) asm volatile("" : "+a"(qf[g][c]));
-            // |q|^2 and metric of the 16 queries whose scores this lane will hold
+            // |q|^2, metric and threshold of the 16 queries whose scores this lane will hold
             const float qn_own = live ? slot_qnorm[slot] : 0.f;
             const bool l2_own = live ? slot_meta[slot].metric == 0u : false;
+            const uint32_t thr_own = FILTER && live ? thr_key[slot] : 0u;
             const uint32_t l2_all = (uint32_t)__ballot(l2_own && lane < 32);
             float qn[16];
+            uint32_t thr[16], cnt[16];
             uint32_t l2mask = 0;
 #pragma unroll
             for (int i = 0; i < 16; ++i) {
                 const uint32_t j = 8 * (i / 4) + 4 * kg + (i % 4);
                 qn[i] = __shfl(qn_own, (int)j, 64);
+                thr[i] = (uint32_t)__shfl((int)thr_own, (int)j, 64);
+                cnt[i] = 0u;
                 l2mask |= ((l2_all >> j) & 1u) << i;
             }
-            const uint32_t npad_bytes = tl.npad * 4u;
+            const uint32_t pitch_bytes = tl.pitch * 4u;
+            // output region of the tile: dense rows of nblocks*32 scores, or (query, chunk) pair regions
             const __amdgpu_buffer_rsrc_t ors = __builtin_amdgcn_make_buffer_rsrc(
-                (void *)(scores + tl.score_off), 0, ((tl.nq - 1) * tl.npad + nblocks * TRI_VB) * 4u, SCAN_BUF_FLAGS);
-            const uint32_t lane_off = 4 * kg * npad_bytes + r * 4;
+                (void *)(out_buf + tl.out_off), 0,
+                ((tl.nq - 1) * tl.pitch + (FILTER ? 2u * len : nblocks * TRI_VB)) * 4u, SCAN_BUF_FLAGS);
+            const uint32_t lane_off = 4 * kg * pitch_bytes + r * 4;
             __builtin_amdgcn_sched_barrier(0);
 
-            uint32_t off = off0;
-            for (uint32_t b = 0; b < nblocks; b += RB) {
+            for (uint32_t b = 0; b < nblocks; ++b, off += blk_bytes) {
+                // |x|^2 of this lane's vector, issued before the prefetches below so that waiting
+                // for it never waits for them (vector-memory operations complete in order)
+                const float vn = __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(nrs, (b * TRI_VB + r) * 4u, 0, 0));
+                __builtin_amdgcn_sched_barrier(0);
+                tri_f32x16 acc;
 #pragma unroll
-                for (int rb = 0; rb < RB; ++rb) {
-                    // |x|^2 of this lane's vector, issued before the prefetches below so that waiting
-                    // for it never waits for them (vector-memory operations complete in order)
-                    const float vn = __uint_as_float(
-                        __builtin_amdgcn_raw_buffer_load_b32(nrs, ((b + rb) * TRI_VB + r) * 4u, 0, 0));
+                for (int i = 0; i < 16; ++i) acc[i] = 0.f;
+#pragma unroll
+                for (int g = 0; g < NG; ++g) {
+                    const int sl = g % RG;
+#pragma unroll
+                    for (int c = 0; c < 4; ++c)
+                        tri_mma32<DT>(acc, make_uint4(qf[g][c].x, qf[g][c].y, qf[g][c].z, qf[g][c].w), buf[sl][c]);
                     __builtin_amdgcn_sched_barrier(0);
-                    tri_f32x16 acc;
+                    const uint32_t nxt = g + RG < NG ? off + (g + RG) * 128 : off + blk_bytes + (g + RG - NG) * 128;
 #pragma unroll
-                    for (int i = 0; i < 16; ++i) acc[i] = 0.f;
-#pragma unroll
-                    for (int g = 0; g < NG; ++g) {
-#pragma unroll
-                        for (int c = 0; c < 4; ++c)
-                            tri_mma32<DT>(acc, make_uint4(qf[g][c].x, qf[g][c].y, qf[g][c].z, qf[g][c].w), buf[rb][g][c]);
-                        __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-                        for (int c = 0; c < 4; ++c)
-                            buf[rb][g][c] = scan_ld16(vrs, off + (RB + rb) * blk_bytes + g * 128 + c * 32);
-                        __builtin_amdgcn_sched_barrier(0);
-                    }
-                    scan_store_block(acc, vn, qn, l2mask, ors, lane_off + (b + rb) * (TRI_VB * 4u), npad_bytes,
-                                     b + rb < nblocks);
+                    for (int c = 0; c < 4; ++c) buf[sl][c] = scan_ld16(vrs, nxt + c * 32);
                     __builtin_amdgcn_sched_barrier(0);
                 }
-                off += RB * blk_bytes;
+                if constexpr (FILTER) {
+                    const uint32_t vpos = b * TRI_VB + r;
+                    scan_filter_block_reg(acc, vn, qn, l2mask, thr, cnt, kg, r, tl.nq, vpos < len, tl.vec_begin + vpos,
+                                          ors, pitch_bytes);
+                } else {
+                    scan_store_block(acc, vn, qn, l2mask, ors, lane_off + b * (TRI_VB * 4u), pitch_bytes, true);
+                }
+                __builtin_amdgcn_sched_barrier(0);
+            }
+            if constexpr (FILTER) {
+                // lane r < 4 of half kg holds query 4*kg + r in cnt[0..3]; queries 8.. in cnt[4..], and so on
+#pragma unroll
+                for (int i = 0; i < 16; ++i) {
+                    const uint32_t j = 8 * (i / 4) + 4 * kg + (i % 4);
+                    if (r == 0 && j < tl.nq) surv_count[(tl.item_pos + j) * TRI_TILES_PER_ITEM + tl.chunk] = cnt[i];
+                }
             }
         }
         t = __builtin_amdgcn_readfirstlane(t_next);
@@ -191,6 +279,8 @@ struct ScanShared {
     uint32_t slot[TRI_QT];
     float qnorm[TRI_QT];
     uint32_t metric[TRI_QT];
+    uint32_t thr[TRI_QT];
+    uint32_t cnt[TRI_QT];
     uint32_t tile;
 };
 
@@ -198,9 +288,9 @@ struct ScanShared {
 // wavefront's blocks b = wave, wave+4, ... form ONE stream of (block, group) steps: while group g is
 // multiplied, the loads of the group SCAN_RING steps ahead -- in this block or the wavefront's next
 // one -- are already in flight, so the stream does not drain at block boundaries.
-template <int DT, int NG>
+template <int DT, int NG, bool FILTER>
 __device__ __forceinline__ void scan_tile_pipelined(const TriTile &tl, const uint8_t *__restrict__ qlds,
-                                                    uint32_t pitch, const ScanShared &sh, float *__restrict__ scores)
+                                                    uint32_t pitch, ScanShared &sh, float *__restrict__ out_buf)
 {
     static_assert(NG % SCAN_RING == 0, "ring slots must line up across blocks");
     const uint32_t lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -221,10 +311,11 @@ __device__ __forceinline__ void scan_tile_pipelined(const TriTile &tl, const uin
         qn[i] = sh.qnorm[j];
         l2mask |= (sh.metric[j] == 0u ? 1u : 0u) << i;
     }
-    const uint32_t npad_bytes = tl.npad * 4u;
+    const uint32_t pitch_bytes = tl.pitch * 4u;
     const __amdgpu_buffer_rsrc_t ors = __builtin_amdgcn_make_buffer_rsrc(
-        (void *)(scores + tl.score_off), 0, ((tl.nq - 1) * tl.npad + nblocks * TRI_VB) * 4u, SCAN_BUF_FLAGS);
-    const uint32_t lane_off = 4 * kg * npad_bytes + r * 4;
+        (void *)(out_buf + tl.out_off), 0, ((tl.nq - 1) * tl.pitch + (FILTER ? 2u * len : nblocks * TRI_VB)) * 4u,
+        SCAN_BUF_FLAGS);
+    const uint32_t lane_off = 4 * kg * pitch_bytes + r * 4;
     constexpr uint32_t bstride = (TRI_SCAN_THREADS / 64) * TRI_VB * row_bytes;   // to the wavefront's next block
 
     uint32_t off = (wave * TRI_VB + r) * row_bytes + kg * 16;
@@ -256,16 +347,20 @@ __device__ __forceinline__ void scan_tile_pipelined(const TriTile &tl, const uin
             for (int c = 0; c < 4; ++c) buf[s][c] = scan_ld16(vrs, nxt + c * 32);
             __builtin_amdgcn_sched_barrier(0);
         }
-        scan_store_block(acc, vn, qn, l2mask, ors, lane_off + b * (TRI_VB * 4u), npad_bytes, true);
+        if constexpr (FILTER)
+            scan_filter_block(acc, vn, qn, l2mask, sh.thr, sh.cnt, kg, tl.nq, b * TRI_VB + r < len,
+                              tl.vec_begin + b * TRI_VB + r, ors, pitch_bytes);
+        else
+            scan_store_block(acc, vn, qn, l2mask, ors, lane_off + b * (TRI_VB * 4u), pitch_bytes, true);
         __builtin_amdgcn_sched_barrier(0);
     }
 }
 
 // Any row length: same arithmetic, the groups of a block are loaded SCAN_RING at a time without
 // overlap across blocks.
-template <int DT>
+template <int DT, bool FILTER>
 __device__ __forceinline__ void scan_tile_generic(const TriTile &tl, const uint8_t *__restrict__ qlds, uint32_t pitch,
-                                                  const ScanShared &sh, float *__restrict__ scores)
+                                                  ScanShared &sh, float *__restrict__ out_buf)
 {
     const uint32_t lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const uint32_t r = lane & 31, kg = lane >> 5;
@@ -286,10 +381,11 @@ __device__ __forceinline__ void scan_tile_generic(const TriTile &tl, const uint8
         qn[i] = sh.qnorm[j];
         l2mask |= (sh.metric[j] == 0u ? 1u : 0u) << i;
     }
-    const uint32_t npad_bytes = tl.npad * 4u;
+    const uint32_t pitch_bytes = tl.pitch * 4u;
     const __amdgpu_buffer_rsrc_t ors = __builtin_amdgcn_make_buffer_rsrc(
-        (void *)(scores + tl.score_off), 0, ((tl.nq - 1) * tl.npad + nblocks * TRI_VB) * 4u, SCAN_BUF_FLAGS);
-    const uint32_t lane_off = 4 * kg * npad_bytes + r * 4;
+        (void *)(out_buf + tl.out_off), 0, ((tl.nq - 1) * tl.pitch + (FILTER ? 2u * len : nblocks * TRI_VB)) * 4u,
+        SCAN_BUF_FLAGS);
+    const uint32_t lane_off = 4 * kg * pitch_bytes + r * 4;
 
     for (uint32_t b = wave; b < nblocks; b += TRI_SCAN_THREADS / 64) {
         const uint32_t off = (b * TRI_VB + r) * row_bytes + kg * 16;
@@ -314,20 +410,25 @@ __device__ __forceinline__ void scan_tile_generic(const TriTile &tl, const uint8
                 }
             }
         }
-        scan_store_block(acc, vn, qn, l2mask, ors, lane_off + b * (TRI_VB * 4u), npad_bytes, true);
+        if constexpr (FILTER)
+            scan_filter_block(acc, vn, qn, l2mask, sh.thr, sh.cnt, kg, tl.nq, b * TRI_VB + r < len,
+                              tl.vec_begin + b * TRI_VB + r, ors, pitch_bytes);
+        else
+            scan_store_block(acc, vn, qn, l2mask, ors, lane_off + b * (TRI_VB * 4u), pitch_bytes, true);
     }
 }
 
-template <int DT, int NG>
+template <int DT, int NG, bool FILTER>
 __global__ __launch_bounds__(TRI_SCAN_THREADS) __attribute__((amdgpu_waves_per_eu(2, 3))) void scan_lds_kernel(
-    const TriTile *__restrict__ tiles, const TriStepDev *__restrict__ step_dev, uint32_t *__restrict__ tile_counter,
+    const TriTile *__restrict__ tiles, const uint32_t *__restrict__ n_tiles_ptr, uint32_t *__restrict__ tile_counter,
     uint32_t my_class, const uint32_t *__restrict__ sorted_slot, const uint8_t *__restrict__ slot_query,
     uint32_t slot_row_bytes, uint32_t n_slots, const TriSlotMeta *__restrict__ slot_meta,
-    const float *__restrict__ slot_qnorm, float *__restrict__ scores)
+    const float *__restrict__ slot_qnorm, const uint32_t *__restrict__ thr_key, uint32_t *__restrict__ surv_count,
+    float *__restrict__ out_buf)
 {
     extern __shared__ __attribute__((aligned(16))) uint8_t qlds[];
     __shared__ ScanShared sh;
-    const uint32_t n_tiles = step_dev->n_tiles;
+    const uint32_t n_tiles = *n_tiles_ptr;
     for (;;) {
         __syncthreads();                        // previous tile's LDS reads are done
         if (threadIdx.x == 0) sh.tile = atomicAdd(tile_counter, 1u);
@@ -343,6 +444,8 @@ __global__ __launch_bounds__(TRI_SCAN_THREADS) __attribute__((amdgpu_waves_per_e
             sh.slot[j] = slot;
             sh.qnorm[j] = slot != 0xFFFFFFFFu ? slot_qnorm[slot] : 0.f;
             sh.metric[j] = slot != 0xFFFFFFFFu ? slot_meta[slot].metric : 1u;
+            sh.thr[j] = FILTER && slot != 0xFFFFFFFFu ? thr_key[slot] : 0u;
+            sh.cnt[j] = 0u;
         }
         __syncthreads();
         // stage the tile's query rows; rows past nq are zero (masked padding)
@@ -356,64 +459,76 @@ __global__ __launch_bounds__(TRI_SCAN_THREADS) __attribute__((amdgpu_waves_per_e
         }
         __syncthreads();
         if constexpr (NG != 0)
-            scan_tile_pipelined<DT, NG>(tl, qlds, pitch, sh, scores);
+            scan_tile_pipelined<DT, NG, FILTER>(tl, qlds, pitch, sh, out_buf);
         else
-            scan_tile_generic<DT>(tl, qlds, pitch, sh, scores);
+            scan_tile_generic<DT, FILTER>(tl, qlds, pitch, sh, out_buf);
+        if constexpr (FILTER) {
+            __syncthreads();                    // every wavefront has appended its candidates
+            if (threadIdx.x < tl.nq)
+                surv_count[(tl.item_pos + threadIdx.x) * TRI_TILES_PER_ITEM + tl.chunk] = sh.cnt[threadIdx.x];
+        }
     }
 }
 
 // ================================================================================ launch
-typedef void (*scan_fn)(const TriTile *, const TriStepDev *, uint32_t *, uint32_t, const uint32_t *, const uint8_t *,
-                        uint32_t, uint32_t, const TriSlotMeta *, const float *, float *);
+typedef void (*scan_fn)(const TriTile *, const uint32_t *, uint32_t *, uint32_t, const uint32_t *, const uint8_t *,
+                        uint32_t, uint32_t, const TriSlotMeta *, const float *, const uint32_t *, uint32_t *, float *);
 
 struct ScanVariant {
     scan_fn fn;
-    bool wave;      // scan_wave_kernel (64 threads, no LDS) or scan_lds_kernel
+    bool wave;      // scan_wave_kernel (64 threads, no query tile in LDS) or scan_lds_kernel
 };
 
 // class = storage type * 5 + (0: other row length, 1..4: 512, 1024, 1536, 2048 bytes per row)
+template <bool FILTER>
 static ScanVariant scan_variant(uint32_t klass)
 {
     switch (klass) {
-    case 0: return {scan_lds_kernel<TRI_DT_F32, 0>, false};
-    case 1: return {scan_wave_kernel<TRI_DT_F32, 4, 3>, true};
-    case 2: return {scan_wave_kernel<TRI_DT_F32, 8, 1>, true};
-    case 3: return {scan_lds_kernel<TRI_DT_F32, 12>, false};   // (the register-resident form would spill)
-    case 4: return {scan_lds_kernel<TRI_DT_F32, 16>, false};
-    case 5: return {scan_lds_kernel<TRI_DT_F16, 0>, false};
-    case 6: return {scan_wave_kernel<TRI_DT_F16, 4, 3>, true};
-    case 7: return {scan_wave_kernel<TRI_DT_F16, 8, 1>, true};
-    case 8: return {scan_wave_kernel<TRI_DT_F16, 12, 1>, true};
-    default: return {scan_lds_kernel<TRI_DT_F16, 16>, false};
+    case 0: return {scan_lds_kernel<TRI_DT_F32, 0, FILTER>, false};
+    case 1: return {scan_wave_kernel<TRI_DT_F32, 4, 4, FILTER>, true};
+    case 2: return {scan_wave_kernel<TRI_DT_F32, 8, 4, FILTER>, true};
+    case 3: return {scan_lds_kernel<TRI_DT_F32, 12, FILTER>, false};   // (the register-resident form would spill)
+    case 4: return {scan_lds_kernel<TRI_DT_F32, 16, FILTER>, false};
+    case 5: return {scan_lds_kernel<TRI_DT_F16, 0, FILTER>, false};
+    case 6: return {scan_wave_kernel<TRI_DT_F16, 4, 4, FILTER>, true};
+    case 7: return {scan_wave_kernel<TRI_DT_F16, 8, 4, FILTER>, true};
+    case 8: return {scan_wave_kernel<TRI_DT_F16, 12, 6, FILTER>, true};
+    default: return {scan_lds_kernel<TRI_DT_F16, 16, FILTER>, false};
     }
 }
 
-static uint32_t g_scan_lds_limit[TRI_SCAN_CLASSES] = {};
+static uint32_t g_scan_lds_limit[2 * TRI_SCAN_CLASSES] = {};
 
-// Launch the scan kernels of one step: one per class present in class_mask, each a persistent grid
-// sized to what the chip holds at once.
-hipError_t tri_launch_scan(const TriLaunchCtx &c, const TriDevWs &ws, uint32_t max_row_bytes, uint32_t class_mask)
+// Launch the scan kernels of one step -- the sample launch or the main launch -- one kernel per class
+// present in class_mask, each a persistent grid sized to what the chip holds at once.
+hipError_t tri_launch_scan(const TriLaunchCtx &c, const TriDevWs &ws, uint32_t max_row_bytes, uint32_t class_mask,
+                           bool sample)
 {
+    const TriTile *tiles = sample ? ws.stiles : ws.tiles;
+    const uint32_t *n_ptr = sample ? &ws.step_dev->n_sample_tiles : &ws.step_dev->n_tiles;
+    float *out = sample ? ws.sample_scores : ws.scores;
     for (uint32_t k = 0; k < TRI_SCAN_CLASSES; ++k) {
         if (!(class_mask & (1u << k))) continue;
-        const ScanVariant v = scan_variant(k);
+        const ScanVariant v = sample ? scan_variant<false>(k) : scan_variant<true>(k);
+        uint32_t *counter = ws.tile_counter + (sample ? TRI_SCAN_CLASSES : 0) + k;
         if (v.wave) {
             // one wavefront per SIMD: 4 per compute unit
-            hipLaunchKernelGGL(v.fn, dim3(c.n_cu * 4), dim3(64), 0, c.stream, ws.tiles, ws.step_dev,
-                               ws.tile_counter + k, k, ws.sorted_slot, ws.slot_query, c.slot_row_bytes, c.S,
-                               ws.slot_meta, ws.slot_qnorm, ws.scores);
+            hipLaunchKernelGGL(v.fn, dim3(c.n_cu * 4), dim3(64), 0, c.stream, tiles, n_ptr, counter, k, ws.sorted_slot,
+                               ws.slot_query, c.slot_row_bytes, c.S, ws.slot_meta, ws.slot_qnorm, ws.thr_key,
+                               ws.surv_count, out);
         } else {
             const uint32_t lds = TRI_QT * (max_row_bytes + 16);
             uint32_t per_cu = (160u * 1024u - 1024u) / (lds + 1024u);
             per_cu = per_cu < 1 ? 1 : (per_cu > 3 ? 3 : per_cu);
-            if (lds > g_scan_lds_limit[k]) {
+            uint32_t &limit = g_scan_lds_limit[(sample ? TRI_SCAN_CLASSES : 0) + k];
+            if (lds > limit) {
                 hipError_t e = hipFuncSetAttribute((const void *)v.fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
                 if (e != hipSuccess) return e;
-                g_scan_lds_limit[k] = lds;
+                limit = lds;
             }
-            hipLaunchKernelGGL(v.fn, dim3(c.n_cu * per_cu), dim3(TRI_SCAN_THREADS), lds, c.stream, ws.tiles,
-                               ws.step_dev, ws.tile_counter + k, k, ws.sorted_slot, ws.slot_query, c.slot_row_bytes,
-                               c.S, ws.slot_meta, ws.slot_qnorm, ws.scores);
+            hipLaunchKernelGGL(v.fn, dim3(c.n_cu * per_cu), dim3(TRI_SCAN_THREADS), lds, c.stream, tiles, n_ptr, counter,
+                               k, ws.sorted_slot, ws.slot_query, c.slot_row_bytes, c.S, ws.slot_meta, ws.slot_qnorm,
+                               ws.thr_key, ws.surv_count, out);
         }
     }
     return hipGetLastError();

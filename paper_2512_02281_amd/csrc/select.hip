@@ -25,27 +25,18 @@
 #define SEL_CAP 4096      // (key, id) pairs sorted in LDS
 #define SEL_SAMPLE 1024   // target size of the key sample (at most SEL_CAP keys are kept)
 
-__device__ __forceinline__ uint32_t sel_key(float f, uint32_t desc)
-{
-    uint32_t u = __float_as_uint(f);
-    if (u == 0x80000000u) u = 0;                       // -0 and +0 are the same score
-    u ^= (u >> 31) ? 0xFFFFFFFFu : 0x80000000u;        // ascending float order -> ascending unsigned
-    return desc ? ~u : u;
-}
+__device__ __forceinline__ uint32_t sel_key(float f, uint32_t desc) { return tri_score_key(f, desc); }
+__device__ __forceinline__ float sel_unkey(uint32_t key, uint32_t desc) { return tri_key_score(key, desc); }
 
-__device__ __forceinline__ float sel_unkey(uint32_t key, uint32_t desc)
-{
-    uint32_t u = desc ? ~key : key;
-    u ^= (u >> 31) ? 0x80000000u : 0xFFFFFFFFu;
-    return __uint_as_float(u);
-}
-
-// A candidate source: segments of (scores, ids).  ids == nullptr means id = id_base + position.
+// A candidate source: segments.  Dense segment: scores[i], id = ids ? ids[i] : id_base + i.
+// Pair segment (pairs != 0): scores points at (score bits, position) pairs, id = ids[position].
 struct SelSeg {
     const float *scores;
     const uint32_t *ids;
     uint32_t len;
     uint32_t id_base;
+    uint32_t pairs;
+    uint32_t pad_;
 };
 
 struct SelShared {
@@ -56,7 +47,8 @@ struct SelShared {
     uint32_t digit, need, count, cnt;
 };
 
-__device__ __forceinline__ uint32_t sel_id(const SelSeg &sg, uint32_t i) { return sg.ids ? sg.ids[i] : sg.id_base + i; }
+// `where` is what sel_for_each hands to its callback: the element's index (dense) or stored position (pairs)
+__device__ __forceinline__ uint32_t sel_id(const SelSeg &sg, uint32_t where) { return sg.ids ? sg.ids[where] : sg.id_base + where; }
 
 // Inclusive scan of one value per thread across the workgroup (TRI_SEL_THREADS threads).
 __device__ __forceinline__ uint32_t sel_block_scan_incl(uint32_t v, uint32_t *wave_tot)
@@ -125,13 +117,25 @@ __device__ __forceinline__ void sel_for_each(const SelSeg *cache, uint32_t nseg,
         const uint32_t nch = (n + CH - 1) / CH;
         while (next < base + nch) {
             const uint32_t i0 = (next - base) * CH + lane;
-            float v[SEL_UNROLL];
+            if (sg.pairs) {
+                const uint2 *pp = (const uint2 *)sg.scores;
+                uint2 v[SEL_UNROLL];
 #pragma unroll
-            for (int u = 0; u < SEL_UNROLL; ++u) v[u] = i0 + u * 64 < n ? sg.scores[i0 + u * 64] : 0.f;
+                for (int u = 0; u < SEL_UNROLL; ++u) v[u] = i0 + u * 64 < n ? pp[i0 + u * 64] : make_uint2(0u, 0u);
 #pragma unroll
-            for (int u = 0; u < SEL_UNROLL; ++u) {
-                const bool valid = i0 + u * 64 < n;
-                f(valid, valid ? sel_key(v[u], desc) : 0xFFFFFFFFu, sg, i0 + u * 64);
+                for (int u = 0; u < SEL_UNROLL; ++u) {
+                    const bool valid = i0 + u * 64 < n;
+                    f(valid, valid ? sel_key(__uint_as_float(v[u].x), desc) : 0xFFFFFFFFu, sg, v[u].y);
+                }
+            } else {
+                float v[SEL_UNROLL];
+#pragma unroll
+                for (int u = 0; u < SEL_UNROLL; ++u) v[u] = i0 + u * 64 < n ? sg.scores[i0 + u * 64] : 0.f;
+#pragma unroll
+                for (int u = 0; u < SEL_UNROLL; ++u) {
+                    const bool valid = i0 + u * 64 < n;
+                    f(valid, valid ? sel_key(v[u], desc) : 0xFFFFFFFFu, sg, i0 + u * 64);
+                }
             }
             next += TRI_SEL_THREADS / 64;
         }
@@ -318,7 +322,7 @@ __global__ __launch_bounds__(TRI_SEL_THREADS) void coarse_select_kernel(
     __shared__ SelShared sh;
     const TriNewDesc d = desc[first_new + blockIdx.x];
     const float *row = scores + (size_t)blockIdx.x * ldc;
-    auto seg_of = [&](uint32_t) { return SelSeg{row, nullptr, nlist, 0u}; };
+    auto seg_of = [&](uint32_t) { return SelSeg{row, nullptr, nlist, 0u, 0u, 0u}; };
     const uint32_t n = sel_block_topk(sh, 1u, seg_of, nlist, d.nprobe, d.metric);
     uint32_t *dst = probe + (size_t)d.slot * nprobe_max;
     for (uint32_t i = threadIdx.x; i < n; i += TRI_SEL_THREADS) dst[i] = (uint32_t)(sh.pool[i] & 0xFFFFFFFFu);
@@ -334,15 +338,72 @@ hipError_t tri_launch_coarse_select(const TriLaunchCtx &c, const TriDevWs &ws, c
 }
 
 // ------------------------------------------------------------------------------------------------
-// Slot merge: one workgroup per running slot of the step.  Candidates = the score segments of the
-// slot's work items of this step + its running top-k.  Output = new running top-k, or -- when the
-// slot retires in this step -- its final result record.
+// Threshold of each running slot for this step's scan: the k-th best key among the slot's sample
+// scores (the first TRI_SAMPLE_VECS vectors of up to TRI_THRESH_ITEMS of its lists) and its running
+// top-k -- a subset of its candidates, so nothing of its final top-k lies beyond it.  Fewer than k
+// such keys: no filtering (all-ones).
+__global__ __launch_bounds__(TRI_SEL_THREADS) void slot_threshold_kernel(
+    const TriPlanEntry *__restrict__ plan, const TriSlotMeta *__restrict__ slot_meta,
+    const uint32_t *__restrict__ item_glist, const uint32_t *__restrict__ item_sorted_pos,
+    const uint32_t *__restrict__ glist_len, const float *__restrict__ sample_scores,
+    const float *__restrict__ topk_score, const uint32_t *__restrict__ topk_count, uint32_t kmax,
+    uint32_t *__restrict__ thr_key)
+{
+    __shared__ SelShared sh;
+    const TriPlanEntry e = plan[blockIdx.x];
+    const TriSlotMeta meta = slot_meta[e.slot];
+    const uint32_t desc = meta.metric == 1u;
+    const uint32_t have = e.cursor > 0 ? topk_count[e.slot] : 0u;
+    const uint32_t nitems = e.take < TRI_THRESH_ITEMS ? e.take : TRI_THRESH_ITEMS;
+    uint32_t *keys = (uint32_t *)sh.pool;                  // room for 2 * SEL_CAP keys
+    if (threadIdx.x == 0) sh.cnt = 0;
+    __syncthreads();
+    // wavefronts take items round-robin; lanes 0..31 the item's sample row
+    const uint32_t lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    for (uint32_t s = wave; s < nitems; s += TRI_SEL_THREADS / 64) {
+        const uint32_t it = e.item_base + s;
+        const uint32_t n = min(glist_len[item_glist[it]], (uint32_t)TRI_SAMPLE_VECS);
+        const bool valid = lane < n;
+        const float v = valid ? sample_scores[(size_t)item_sorted_pos[it] * TRI_SAMPLE_VECS + lane] : 0.f;
+        const uint32_t pos = sel_append_pos(valid, &sh.cnt);
+        if (valid) keys[pos] = sel_key(v, desc);
+    }
+    for (uint32_t i0 = wave * 64; i0 < have; i0 += TRI_SEL_THREADS) {
+        const bool valid = i0 + lane < have;
+        const float v = valid ? topk_score[(size_t)e.slot * kmax + i0 + lane] : 0.f;
+        const uint32_t pos = sel_append_pos(valid, &sh.cnt);
+        if (valid) keys[pos] = sel_key(v, desc);
+    }
+    __syncthreads();
+    const uint32_t n = sh.cnt;                             // <= 96 * 32 + 1024 = SEL_CAP
+    uint32_t thr = 0xFFFFFFFFu;
+    if (n >= meta.k) {
+        sel_bitonic(keys, n);
+        thr = keys[meta.k - 1];
+    }
+    if (threadIdx.x == 0) thr_key[e.slot] = thr;
+}
+
+hipError_t tri_launch_threshold(const TriLaunchCtx &c, const TriDevWs &ws, const TriPlanEntry *plan_dev, uint32_t n_plan)
+{
+    if (n_plan == 0) return hipSuccess;
+    hipLaunchKernelGGL(slot_threshold_kernel, dim3(n_plan), dim3(TRI_SEL_THREADS), 0, c.stream, plan_dev, ws.slot_meta,
+                       ws.item_glist, ws.item_sorted_pos, ws.glist_len, ws.sample_scores, ws.topk_score, ws.topk_count,
+                       c.kmax, ws.thr_key);
+    return hipGetLastError();
+}
+
+// ------------------------------------------------------------------------------------------------
+// Slot merge: one workgroup per running slot of the step.  Candidates = the (score, position) pairs
+// the scan kept for the slot's work items of this step, one segment per (item, chunk), + its running
+// top-k.  Output = new running top-k, or -- when the slot retires in this step -- its final result.
 __global__ __launch_bounds__(TRI_SEL_THREADS) void slot_merge_kernel(
     const TriPlanEntry *__restrict__ plan, const TriSlotMeta *__restrict__ slot_meta,
     const TriIndexDev *__restrict__ indexes, const uint32_t *__restrict__ item_glist,
-    const uint64_t *__restrict__ item_score_off, const uint32_t *__restrict__ glist_len,
+    const uint64_t *__restrict__ item_score_off, const uint32_t *__restrict__ item_sorted_pos,
+    const uint32_t *__restrict__ surv_count, uint32_t chunk_vecs, const uint32_t *__restrict__ glist_len,
     const uint32_t *__restrict__ glist_voff, const uint32_t *__restrict__ glist_index,
-    const float *__restrict__ scores, float *__restrict__ topk_score, uint32_t *__restrict__ topk_id,
+    const float *__restrict__ cand, float *__restrict__ topk_score, uint32_t *__restrict__ topk_id,
     uint32_t *__restrict__ topk_count, uint32_t kmax, uint32_t *__restrict__ res_block,
     const uint32_t *__restrict__ probe, uint32_t nprobe_max, uint32_t *__restrict__ res_probes)
 {
@@ -354,22 +415,27 @@ __global__ __launch_bounds__(TRI_SEL_THREADS) void slot_merge_kernel(
     const uint32_t have = e.cursor > 0 ? topk_count[e.slot] : 0u;
     float *run_score = topk_score + (size_t)e.slot * kmax;
     uint32_t *run_id = topk_id + (size_t)e.slot * kmax;
-    const uint32_t nseg = e.take + (have ? 1u : 0u);
+    const uint32_t nlist_seg = e.take * TRI_TILES_PER_ITEM;
+    const uint32_t nseg = nlist_seg + (have ? 1u : 0u);
 
+    // segment s < nlist_seg: chunk s % 4 of item s / 4 (empty when the list has fewer chunks)
     auto seg_of = [&](uint32_t s) {
-        if (s < e.take) {
-            const uint32_t it = e.item_base + s;
+        if (s < nlist_seg) {
+            const uint32_t it = e.item_base + s / TRI_TILES_PER_ITEM, ch = s % TRI_TILES_PER_ITEM;
             const uint32_t g = item_glist[it];
+            const uint32_t nch = (glist_len[g] + chunk_vecs - 1) / chunk_vecs;
+            if (ch >= nch) return SelSeg{cand, nullptr, 0u, 0u, 1u, 0u};
             const TriIndexDev &ix = indexes[glist_index[g]];
-            return SelSeg{scores + item_score_off[it], ix.ids + glist_voff[g], glist_len[g], 0u};
+            return SelSeg{cand + item_score_off[it] + 2u * (size_t)ch * chunk_vecs, ix.ids + glist_voff[g],
+                          surv_count[item_sorted_pos[it] * TRI_TILES_PER_ITEM + ch], 0u, 1u, 0u};
         }
-        return SelSeg{run_score, run_id, have, 0u};
+        return SelSeg{run_score, run_id, have, 0u, 0u, 0u};
     };
     // total number of candidates
     if (threadIdx.x == 0) sh_total = have;
     __syncthreads();
     uint32_t part = 0;
-    for (uint32_t s = threadIdx.x; s < e.take; s += TRI_SEL_THREADS) part += glist_len[item_glist[e.item_base + s]];
+    for (uint32_t s = threadIdx.x; s < nlist_seg; s += TRI_SEL_THREADS) part += seg_of(s).len;
     if (part) atomicAdd(&sh_total, part);
     __syncthreads();
     const uint32_t total = sh_total;
@@ -400,12 +466,12 @@ __global__ __launch_bounds__(TRI_SEL_THREADS) void slot_merge_kernel(
 }
 
 hipError_t tri_launch_merge(const TriLaunchCtx &c, const TriDevWs &ws, const TriPlanEntry *plan_dev, uint32_t n_plan,
-                            bool keep_probes)
+                            bool keep_probes, uint32_t chunk_vecs)
 {
     if (n_plan == 0) return hipSuccess;
     hipLaunchKernelGGL(slot_merge_kernel, dim3(n_plan), dim3(TRI_SEL_THREADS), 0, c.stream, plan_dev, ws.slot_meta,
-                       ws.indexes, ws.item_glist, ws.item_score_off, ws.glist_len, ws.glist_voff, ws.glist_index,
-                       ws.scores, ws.topk_score, ws.topk_id, ws.topk_count, c.kmax, ws.res_block, ws.probe,
-                       c.nprobe_max, keep_probes ? ws.res_probes : (uint32_t *)nullptr);
+                       ws.indexes, ws.item_glist, ws.item_score_off, ws.item_sorted_pos, ws.surv_count, chunk_vecs,
+                       ws.glist_len, ws.glist_voff, ws.glist_index, ws.scores, ws.topk_score, ws.topk_id, ws.topk_count,
+                       c.kmax, ws.res_block, ws.probe, c.nprobe_max, keep_probes ? ws.res_probes : (uint32_t *)nullptr);
     return hipGetLastError();
 }

@@ -36,7 +36,7 @@ int fail(int code, const char *fmt, ...)
     } while (0)
 
 constexpr uint32_t RING = 4;          // steps that may be in flight before search_step waits
-constexpr uint32_t N_EV = 6;          // profile events per step
+constexpr uint32_t N_EV = 7;          // profile events per step
 
 inline uint32_t round_up(uint32_t v, uint32_t m) { return (v + m - 1) / m * m; }
 inline size_t round_up_sz(size_t v, size_t m) { return (v + m - 1) / m * m; }
@@ -165,13 +165,19 @@ size_t carve(const tri_pool_cfg &c, uint32_t max_row_bytes, uint32_t coarse_rows
     CARVE(item_slot, uint32_t *, W * 4)
     CARVE(item_rank, uint32_t *, W * 4)
     CARVE(item_score_off, uint64_t *, W * 8)
+    CARVE(item_sorted_pos, uint32_t *, W * 4)
     CARVE(sorted_slot, uint32_t *, W * 4)
     CARVE(hist, uint32_t *, G * 4)
     CARVE(list_start, uint32_t *, G * 4)
     CARVE(tile_base, uint32_t *, G * 4)
+    CARVE(stile_base, uint32_t *, G * 4)
     CARVE(score_base, uint64_t *, G * 8)
     CARVE(tiles, TriTile *, (size_t)TRI_TILES_PER_ITEM * W * sizeof(TriTile))
+    CARVE(stiles, TriTile *, W * sizeof(TriTile))
     CARVE(tile_counter, uint32_t *, 256)
+    CARVE(surv_count, uint32_t *, (size_t)TRI_TILES_PER_ITEM * W * 4)
+    CARVE(sample_scores, float *, W * (size_t)TRI_SAMPLE_VECS * 4)
+    CARVE(thr_key, uint32_t *, S * 4)
     CARVE(step_dev, TriStepDev *, 256)
     CARVE(scores, float *, (size_t)score_capacity * 4)
     CARVE(res_block, uint32_t *, S * (1 + 2 * (size_t)c.kmax) * 4)
@@ -203,7 +209,7 @@ int derive(const tri_pool_cfg *c, uint32_t *max_row_bytes, uint32_t *coarse_rows
     *coarse_rows = c->coarse_rows ? c->coarse_rows : 1024u;
     if (*coarse_rows > c->slots) *coarse_rows = c->slots;
     *coarse_ldc = round_up(c->max_nlist, 32u);
-    *score_capacity = c->score_capacity ? c->score_capacity : (uint64_t)c->items_per_step * 1024u;
+    *score_capacity = c->score_capacity ? c->score_capacity : (uint64_t)c->items_per_step * 2048u;
     *upload_bytes = round_up_sz((size_t)c->slots * sizeof(TriNewDesc), 256) +
                     round_up_sz((size_t)c->slots * sizeof(TriPlanEntry), 256) + (size_t)c->slots * *max_row_bytes;
     return TRI_OK;
@@ -256,8 +262,9 @@ int reap(tri_pool *P, bool block, uint32_t *finished)
             P->times.admit_ms += ms[0];
             P->times.coarse_ms += ms[1];
             P->times.pack_ms += ms[2];
-            P->times.scan_ms += ms[3];
-            P->times.select_ms += ms[4];
+            P->times.sample_ms += ms[3];
+            P->times.scan_ms += ms[4];
+            P->times.select_ms += ms[5];
             if (R->had_scan) {
                 P->times.scan_launches += 1;
                 P->times.scan_vector_bytes += sd->tile_vec_bytes;
@@ -636,7 +643,7 @@ extern "C" int ivf_build(tri_pool *P, const ivf_params *p, const void *base, uin
     for (uint32_t l = 0; l < nlist; ++l) { h_len[l] = h_off[l + 1] - h_off[l]; maxlen = std::max(maxlen, h_len[l]); }
     if ((uint64_t)maxlen * rb >= (1ull << 31))
         return fail(TRI_EINVAL, "longest list (%u vectors of %u bytes) exceeds 2^31 bytes", maxlen, rb);
-    if ((uint64_t)round_up(maxlen, TRI_VB) > P->score_capacity)
+    if (2ull * round_up(maxlen, TRI_VB) > P->score_capacity)
         return fail(TRI_ENOMEM, "longest list (%u) exceeds the pool's score capacity", maxlen);
     tri_index *ix = new (std::nothrow) tri_index();
     if (!ix) return fail(TRI_ENOMEM, "out of host memory");
@@ -847,7 +854,7 @@ extern "C" int search_step(tri_pool *P, tri_step_stats *st)
         const uint32_t remaining = sl.nprobe - sl.cursor;
         uint32_t take = cfg.lists_per_query_step ? std::min(cfg.lists_per_query_step, remaining) : remaining;
         take = std::min(take, cfg.items_per_step - n_items);
-        const uint64_t per_item = round_up(sl.index->max_list_len, TRI_VB);
+        const uint64_t per_item = 2ull * round_up(sl.index->max_list_len, TRI_VB);   // (score, position) per vector
         if (per_item) take = (uint32_t)std::min<uint64_t>(take, (P->score_capacity - score_used) / per_item);
         if (take == 0) continue;
         TriPlanEntry &e = plan_h[n_plan++];
@@ -912,9 +919,13 @@ extern "C" int search_step(tri_pool *P, tri_step_stats *st)
     if (prof) HIP_TRY(hipEventRecord(R.ev[2], s));
     HIP_TRY(tri_launch_pack(P->ctx, P->ws, plan_d, n_plan, n_items, P->total_lists, P->n_order, P->chunk_vecs));
     if (prof) HIP_TRY(hipEventRecord(R.ev[3], s));
-    if (n_items) HIP_TRY(tri_launch_scan(P->ctx, P->ws, P->attached_row_bytes, P->scan_class_mask));
+    // thresholds: score a sample of every probed list, k-th best of each slot's sample
+    if (n_items) HIP_TRY(tri_launch_scan(P->ctx, P->ws, P->attached_row_bytes, P->scan_class_mask, true));
+    if (n_items) HIP_TRY(tri_launch_threshold(P->ctx, P->ws, plan_d, n_plan));
     if (prof) HIP_TRY(hipEventRecord(R.ev[4], s));
-    HIP_TRY(tri_launch_merge(P->ctx, P->ws, plan_d, n_plan, (cfg.flags & TRI_FLAG_KEEP_PROBES) != 0));
+    if (n_items) HIP_TRY(tri_launch_scan(P->ctx, P->ws, P->attached_row_bytes, P->scan_class_mask, false));
+    if (prof) HIP_TRY(hipEventRecord(R.ev[5], s));
+    HIP_TRY(tri_launch_merge(P->ctx, P->ws, plan_d, n_plan, (cfg.flags & TRI_FLAG_KEEP_PROBES) != 0, P->chunk_vecs));
     if (n_retire) {
         HIP_TRY(hipMemcpyAsync(R.down_host, P->ws.res_block, (size_t)n_retire * (1 + 2 * (size_t)cfg.kmax) * 4,
                                hipMemcpyDeviceToHost, s));
@@ -924,7 +935,7 @@ extern "C" int search_step(tri_pool *P, tri_step_stats *st)
     }
     if (prof) {
         HIP_TRY(hipMemcpyAsync(R.down_host + P->down_step_off, P->ws.step_dev, sizeof(TriStepDev), hipMemcpyDeviceToHost, s));
-        HIP_TRY(hipEventRecord(R.ev[5], s));
+        HIP_TRY(hipEventRecord(R.ev[6], s));
     }
     HIP_TRY(hipEventRecord(R.done, s));
     R.in_use = true;

@@ -53,24 +53,50 @@ struct TriPlanEntry {
 };
 
 // One scan tile: up to TRI_QT queries against one chunk (all of it, for short lists) of one inverted
-// list.  Self-contained: the scan kernels read nothing else about the list.
+// list.  Self-contained: the scan kernels read nothing else about the list.  Two kinds share the layout:
+//  * main tiles: every vector of the chunk is scored, the scores that pass the query's threshold are
+//    appended as (score bits, position in list) pairs to the (query, chunk) region of the candidate buffer;
+//  * sample tiles: only the first TRI_SAMPLE_VECS vectors of the list, all scores written densely.
 struct TriTile {
-    uint64_t vec_addr;    // device address of the chunk's first vector
-    uint64_t vnorm_addr;  // device address of the chunk's first |x|^2
-    uint64_t score_off;   // element offset of the score of (query 0, first vector of the chunk); query j at + j*npad
+    uint64_t vec_addr;    // device address of the first vector
+    uint64_t vnorm_addr;  // device address of its |x|^2
+    uint64_t out_off;     // 4-byte-word offset of query 0's output region (main: in the candidate buffer, its
+                          // chunk part; sample: in the sample buffer); query j at + j * pitch
     uint32_t item_pos;    // first of the tile's queries in the list-sorted item array
     uint32_t nq;          // 1..TRI_QT real queries
-    uint32_t vec_count;   // vectors in the chunk
-    uint32_t npad;        // padded list length = score pitch between queries
+    uint32_t vec_count;   // vectors to score
+    uint32_t pitch;       // words between the regions of consecutive queries
     uint32_t klass;       // which scan kernel serves it (tri_scan_class)
     uint32_t row_bytes;
-    uint32_t pad_[2];
+    uint32_t vec_begin;   // position of the first vector inside its list
+    uint32_t chunk;       // chunk number inside the list (main tiles)
 };
+
+#define TRI_SAMPLE_VECS 32     // vectors per list scored ahead of the scan to find each query's threshold
+#define TRI_THRESH_ITEMS 96    // at most this many items' samples enter one query's threshold
+
+// Order-preserving image of an fp32 score: ascending key = better (bit-flipped for inner product).
+__device__ __forceinline__ uint32_t tri_score_key(float f, uint32_t descending)
+{
+    uint32_t u = __float_as_uint(f);
+    if (u == 0x80000000u) u = 0;                       // -0 and +0 are the same score
+    u ^= (u >> 31) ? 0xFFFFFFFFu : 0x80000000u;        // ascending float order -> ascending unsigned
+    return descending ? ~u : u;
+}
+
+__device__ __forceinline__ float tri_key_score(uint32_t key, uint32_t descending)
+{
+    uint32_t u = descending ? ~key : key;
+    u ^= (u >> 31) ? 0x80000000u : 0xFFFFFFFFu;
+    return __uint_as_float(u);
+}
 
 // Small per-step numbers the device produces for the host (copied back with the results).
 struct TriStepDev {
     uint32_t n_tiles;
     uint32_t n_lists_touched;
+    uint32_t n_sample_tiles;
+    uint32_t pad_;
     uint64_t total_scores;
     uint64_t tile_vec_bytes;    // sum over tiles of list_len * row_bytes
     uint64_t unique_vec_bytes;  // sum over touched lists of list_len * row_bytes
@@ -100,16 +126,22 @@ struct TriDevWs {
     uint32_t *item_glist;     // [W]
     uint32_t *item_slot;      // [W]
     uint32_t *item_rank;      // [W]
-    uint64_t *item_score_off; // [W]
+    uint64_t *item_score_off; // [W] word offset of the item's region in the candidate buffer
+    uint32_t *item_sorted_pos;// [W] position of the item in the list-sorted order
     uint32_t *sorted_slot;    // [W]
     uint32_t *hist;           // [max_total_lists+1]
     uint32_t *list_start;     // [max_total_lists+1]
     uint32_t *tile_base;      // [max_total_lists+1]
+    uint32_t *stile_base;     // [max_total_lists+1] first sample tile of each list
     uint64_t *score_base;     // [max_total_lists+1]
     TriTile *tiles;           // [TRI_TILES_PER_ITEM * W]
-    uint32_t *tile_counter;   // [TRI_SCAN_CLASSES] work-queue heads of the scan kernels
+    TriTile *stiles;          // [W] sample tiles
+    uint32_t *tile_counter;   // [2 * TRI_SCAN_CLASSES] work-queue heads of the scan kernels (main, sample)
+    uint32_t *surv_count;     // [W * TRI_TILES_PER_ITEM] candidates kept per (item, chunk)
+    float *sample_scores;     // [W * TRI_SAMPLE_VECS]
+    uint32_t *thr_key;        // [S] per slot: keys above this cannot reach its top-k
     TriStepDev *step_dev;     // [1]
-    float *scores;            // [score_capacity]
+    float *scores;            // [score_capacity] candidate buffer: per item 2 * npad words of (score bits, position) pairs
     // results of retiring slots, compact, per step
     uint32_t *res_block;      // [S][1 + 2*kmax]  n, ids[kmax], score bits[kmax]
     uint32_t *res_probes;     // [S][nprobe_max]
@@ -135,7 +167,10 @@ hipError_t tri_launch_coarse_select(const TriLaunchCtx &c, const TriDevWs &ws, c
 hipError_t tri_launch_pack(const TriLaunchCtx &c, const TriDevWs &ws, const TriPlanEntry *plan_dev,
                            uint32_t n_plan, uint32_t n_items, uint32_t total_lists, uint32_t n_order,
                            uint32_t chunk_vecs);
-hipError_t tri_launch_scan(const TriLaunchCtx &c, const TriDevWs &ws, uint32_t max_row_bytes, uint32_t class_mask);
+hipError_t tri_launch_scan(const TriLaunchCtx &c, const TriDevWs &ws, uint32_t max_row_bytes, uint32_t class_mask,
+                           bool sample);
+hipError_t tri_launch_threshold(const TriLaunchCtx &c, const TriDevWs &ws, const TriPlanEntry *plan_dev,
+                                uint32_t n_plan);
 #define TRI_TILES_PER_ITEM 4   // tile capacity = 4 W: a list is cut into at most 4 chunks
 
 // Which scan kernel serves an index: 5 classes per storage type (other, 512, 1024, 1536, 2048 bytes per row).
@@ -145,7 +180,7 @@ __host__ __device__ inline uint32_t tri_scan_class(uint32_t dtype, uint32_t row_
     return dtype * 5 + (special ? row_bytes / 512 : 0);
 }
 hipError_t tri_launch_merge(const TriLaunchCtx &c, const TriDevWs &ws, const TriPlanEntry *plan_dev,
-                            uint32_t n_plan, bool keep_probes);
+                            uint32_t n_plan, bool keep_probes, uint32_t chunk_vecs);
 
 // ---- index construction helpers ------------------------------------------------------------
 hipError_t tri_build_pad_rows(hipStream_t s, int dtype, const void *src, uint32_t dim, uint64_t src_pitch_elems,

@@ -329,7 +329,7 @@ def test_config4_full_size_in_the_benchmark_configuration():
     Q = cfg.n_queries
     pool = tri.Pool(slots=Q, items_per_step=Q * cfg.nprobe, lists_per_query_step=0, kmax=128, nprobe_max=cfg.nprobe,
                     max_indexes=1, max_total_lists=cfg.nlist, max_nlist=cfg.nlist, max_dim=cfg.dim,
-                    max_outstanding=Q * 2, coarse_rows=0, flags=tri.TRI_FLAG_KEEP_PROBES, score_capacity=(1 << 30))
+                    max_outstanding=Q * 2, coarse_rows=0, flags=tri.TRI_FLAG_KEEP_PROBES, score_capacity=(1 << 31))
     try:
         _say("config 4: build")
         init = base_t[torch.from_numpy(rows).cuda()].float().cpu().numpy()
