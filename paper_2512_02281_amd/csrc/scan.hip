@@ -111,38 +111,51 @@ __device__ __forceinline__ void scan_filter_block(const tri_f32x16 &acc, float v
     }
 }
 
-// The same for the one-wavefront-per-tile kernel, without LDS round trips and without branches: the
-// running count of candidates of each of the lane's 16 queries lives in a register (identical in the 32
-// lanes of a half-wavefront, which share the query), a ballot gives each passing lane its place behind
-// it, and the 16 stores are issued unconditionally -- lanes that did not pass aim outside the buffer
-// descriptor and are dropped.  Straight-line code: the wavefront never waits for a store.
-__device__ __forceinline__ void scan_filter_block_reg(const tri_f32x16 &acc, float vn, const float (&qn)[16],
-                                                      uint32_t l2mask, const uint32_t (&thr)[16], uint32_t (&cnt)[16],
-                                                      uint32_t kg, uint32_t r, uint32_t nq, bool vec_ok,
-                                                      uint32_t list_pos, __amdgpu_buffer_rsrc_t ors,
-                                                      uint32_t pitch_bytes)
+// The same for the one-wavefront-per-tile kernel.  A store instruction that really writes is costly in
+// the middle of the stream (vector-memory operations of a wavefront retire in order, so every later
+// wait for a prefetched group also waits for the store's acknowledgement from memory), while a block
+// yields only a few dozen candidates.  So candidates are first staged in a wavefront-private LDS
+// array -- no branches, no vector-memory traffic: a ballot gives each passing lane its place, lanes
+// that did not pass write to a per-lane dump entry behind the array -- and leave for the candidate
+// buffer in a burst when the array could not take another full block, or when the tile ends.
+//   entry = (score bits, query row in the tile << 27 | position in the list); positions are below
+//   2^24 (a list is shorter than 2^31 bytes, a row at least 128).
+#define SCAN_STAGE_CAP 4096u            // entries (8 bytes each); a block adds at most TRI_QT * TRI_VB = 1024
+
+__device__ __forceinline__ void scan_stage_block(const tri_f32x16 &acc, float vn, const float (&qn)[16],
+                                                 uint32_t l2mask, const uint32_t (&thr)[16], uint32_t kg, uint32_t lane,
+                                                 uint32_t nq, bool vec_ok, uint32_t list_pos, uint2 *stage,
+                                                 uint32_t &stage_n)
 {
-    float v[16];
-    uint32_t o[16];
-    const uint64_t below = (1ull << r) - 1ull;            // lanes of my half-wavefront before me
 #pragma unroll
     for (int i = 0; i < 16; ++i) {
         const uint32_t j = 8 * (i / 4) + 4 * kg + (i % 4);
         const bool is_l2 = (l2mask >> i) & 1u;
-        v[i] = is_l2 ? (vn + qn[i]) - 2.0f * acc[i] : acc[i];
-        const uint32_t key = tri_score_key(v[i], is_l2 ? 0u : 1u);
+        const float v = is_l2 ? (vn + qn[i]) - 2.0f * acc[i] : acc[i];
+        const uint32_t key = tri_score_key(v, is_l2 ? 0u : 1u);
         const bool pass = vec_ok && j < nq && key <= thr[i];
         const uint64_t m = __ballot(pass);
-        const uint32_t half = kg ? (uint32_t)(m >> 32) : (uint32_t)m;
-        const uint32_t pos = cnt[i] + (uint32_t)__popc(half & (uint32_t)below);
-        o[i] = pass ? j * pitch_bytes + pos * 8u : 0xFFFFFFF8u;
-        cnt[i] += (uint32_t)__popc(half);
+        const uint32_t before = __builtin_amdgcn_mbcnt_hi((uint32_t)(m >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)m, 0u));
+        stage[pass ? stage_n + before : SCAN_STAGE_CAP + lane] = make_uint2(__float_as_uint(v), (j << 27) | list_pos);
+        stage_n += (uint32_t)__popcll(m);
     }
-#pragma unroll
-    for (int i = 0; i < 16; ++i) {
-        const scan_u32x2 pair = {__float_as_uint(v[i]), list_pos};
-        __builtin_amdgcn_raw_buffer_store_b64(pair, ors, o[i], 0, 0);
+}
+
+// Burst of the staged candidates into the (query, chunk) regions of the candidate buffer; qcnt[j] = pairs
+// already in the region of the tile's query j (the order inside a region carries no meaning).
+__device__ __forceinline__ void scan_stage_flush(const uint2 *stage, uint32_t &stage_n, uint32_t *qcnt, uint32_t lane,
+                                                 __amdgpu_buffer_rsrc_t ors, uint32_t pitch_bytes)
+{
+    __builtin_amdgcn_wave_barrier();
+    for (uint32_t e = lane; e < stage_n; e += 64) {
+        const uint2 en = stage[e];
+        const uint32_t j = en.y >> 27;
+        const uint32_t q = atomicAdd(&qcnt[j], 1u);
+        const scan_u32x2 pair = {en.x, en.y & 0x07FFFFFFu};
+        __builtin_amdgcn_raw_buffer_store_b64(pair, ors, j * pitch_bytes + q * 8u, 0, 0);
     }
+    __builtin_amdgcn_wave_barrier();
+    stage_n = 0;
 }
 
 // ================================================================================ wavefront kernel
@@ -165,6 +178,9 @@ __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(1, 1))) void
     const uint32_t n_tiles = *n_tiles_ptr;
     const __amdgpu_buffer_rsrc_t qrs =
         __builtin_amdgcn_make_buffer_rsrc((void *)slot_query, 0, n_slots * slot_row_bytes, SCAN_BUF_FLAGS);
+    // candidate staging of this wavefront (the workgroup IS one wavefront) + 64 dump entries
+    __shared__ uint2 stage[FILTER ? SCAN_STAGE_CAP + 64 : 1];
+    __shared__ uint32_t qcnt[TRI_QT];
 
     uint32_t t = 0;
     if (lane == 0) t = atomicAdd(tile_counter, 1u);
@@ -214,16 +230,17 @@ __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(1, 1))) void
             const uint32_t thr_own = FILTER && live ? thr_key[slot] : 0u;
             const uint32_t l2_all = (uint32_t)__ballot(l2_own && lane < 32);
             float qn[16];
-            uint32_t thr[16], cnt[16];
+            uint32_t thr[16];
             uint32_t l2mask = 0;
 #pragma unroll
             for (int i = 0; i < 16; ++i) {
                 const uint32_t j = 8 * (i / 4) + 4 * kg + (i % 4);
                 qn[i] = __shfl(qn_own, (int)j, 64);
                 thr[i] = (uint32_t)__shfl((int)thr_own, (int)j, 64);
-                cnt[i] = 0u;
                 l2mask |= ((l2_all >> j) & 1u) << i;
             }
+            uint32_t stage_n = 0;
+            if constexpr (FILTER) qcnt[r] = 0u;
             const uint32_t pitch_bytes = tl.pitch * 4u;
             // output region of the tile: dense rows of nblocks*32 scores, or (query, chunk) pair regions
             const __amdgpu_buffer_rsrc_t ors = __builtin_amdgcn_make_buffer_rsrc(
@@ -254,20 +271,18 @@ __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(1, 1))) void
                 }
                 if constexpr (FILTER) {
                     const uint32_t vpos = b * TRI_VB + r;
-                    scan_filter_block_reg(acc, vn, qn, l2mask, thr, cnt, kg, r, tl.nq, vpos < len, tl.vec_begin + vpos,
-                                          ors, pitch_bytes);
+                    if (stage_n > SCAN_STAGE_CAP - TRI_QT * TRI_VB)     // (uniform, and rare: a few dozen pass per block)
+                        scan_stage_flush(stage, stage_n, qcnt, lane, ors, pitch_bytes);
+                    scan_stage_block(acc, vn, qn, l2mask, thr, kg, lane, tl.nq, vpos < len, tl.vec_begin + vpos, stage,
+                                     stage_n);
                 } else {
                     scan_store_block(acc, vn, qn, l2mask, ors, lane_off + b * (TRI_VB * 4u), pitch_bytes, true);
                 }
                 __builtin_amdgcn_sched_barrier(0);
             }
             if constexpr (FILTER) {
-                // lane r < 4 of half kg holds query 4*kg + r in cnt[0..3]; queries 8.. in cnt[4..], and so on
-#pragma unroll
-                for (int i = 0; i < 16; ++i) {
-                    const uint32_t j = 8 * (i / 4) + 4 * kg + (i % 4);
-                    if (r == 0 && j < tl.nq) surv_count[(tl.item_pos + j) * TRI_TILES_PER_ITEM + tl.chunk] = cnt[i];
-                }
+                scan_stage_flush(stage, stage_n, qcnt, lane, ors, pitch_bytes);
+                if (lane < tl.nq) surv_count[(tl.item_pos + lane) * TRI_TILES_PER_ITEM + tl.chunk] = qcnt[lane];
             }
         }
         t = __builtin_amdgcn_readfirstlane(t_next);
