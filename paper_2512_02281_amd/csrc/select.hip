@@ -1,54 +1,77 @@
 // Per-query top-k (the paper's Sec. 3.2 step "scatter (id, dist) back to the owning request and
-// merge into its topM"; here the request's candidates of one step are the score segments of its
-// work items plus its running top-k).
+// merge into its topM"; here the request's candidates of one step are the (score, position) pairs the
+// scan kept for its work items plus its running top-k).
 //
 // Order: ascending 64-bit composite (key << 32 | id), key = order-preserving image of the fp32
 // score (bit-flipped for inner product, so "smaller key" always means "better").  Equal scores are
 // therefore ordered by ascending id, which makes the result independent of how the candidates
 // were batched.
 //
-// One workgroup selects for one query, in LDS:
-//  (1) at most SEL_CAP candidates: all (key, id) pairs are loaded and sorted (bitonic network).
-//  (2) more: a strided sample of about SEL_SAMPLE keys is sorted; the sample's m-th key, with m
-//      five standard deviations above the expected rank of the k-th best, is a threshold that almost
-//      surely admits at least k and far fewer than SEL_CAP candidates; ONE pass over the candidates
-//      collects those not worse than it, and they are sorted as in (1).  Whatever the sample says,
-//      the result is exact whenever the pass collected between k and SEL_CAP candidates: the k best
-//      of the collected set are then the k best of all.
-//  (3) otherwise (heavy ties, adversarial order): three histogram passes (11 + 11 + 10 bits) find
-//      the key T of the k-th best element; if more elements equal T than are still needed, three more
-//      passes over the ids of those elements find the largest id to keep; one pass gathers exactly k.
+// One workgroup selects for one query, in LDS.  Sorting networks over thousands of elements cost a
+// hundred barriers; here sorting is kept for the few elements that survive a bucket cut:
+//  * k best of n <= SEL_CAP composites in LDS (sel_pool_topk): 2048 buckets, linear in the key between
+//    the smallest and largest key present; a prefix sum finds the bucket B that holds rank k; the
+//    elements of buckets <= B (k plus a handful) are compacted and sorted -- by counting ranks when
+//    they are at most 256 (one element per thread, no barriers inside), else by a bitonic network.
+//    Degenerate inputs (everything in one bucket) fall back to the network over all n.
+//  * a bound for rank m among n keys in LDS (sel_keys_threshold): same buckets; the result is the
+//    largest key of bucket B, so at least m keys are not above it, and only a few more.
+//  * candidate sets larger than SEL_CAP: a sample of about SEL_SAMPLE keys gives, through the bound
+//    above, a threshold that almost surely admits at least k and far fewer than SEL_CAP candidates; ONE
+//    pass collects those not worse than it.  Whatever the sample says, the result is exact whenever the
+//    pass collected between k and SEL_CAP candidates: the k best of the collected set are then the k
+//    best of all.
+//  * otherwise (heavy ties, adversarial order): three histogram passes (11 + 11 + 10 bits) find
+//    the key T of the k-th best element; if more elements equal T than are still needed, three more
+//    passes over the ids of those elements find the largest id to keep; one pass gathers exactly k.
 #include "tri_common.h"
 
 #define SEL_BINS 2048
-#define SEL_SEGCACHE 256   // segment descriptors cached in LDS
-#define SEL_CAP 4096      // (key, id) pairs sorted in LDS
-#define SEL_SAMPLE 1024   // target size of the key sample (at most SEL_CAP keys are kept)
+#define SEL_SEGCACHE 544   // pair-segment descriptors cached in LDS (128 lists x 4 chunks, and some)
+#define SEL_CAP 4096       // composites held in LDS
+#define SEL_SMALL 1024     // composites in the second array (which shares its storage with the histogram)
+#define SEL_RANK_MAX 256   // sorted by rank counting up to here (one element per thread)
+#define SEL_SAMPLE 1024    // target size of the key sample
+#define SEL_UNROLL 8
 
 __device__ __forceinline__ uint32_t sel_key(float f, uint32_t desc) { return tri_score_key(f, desc); }
 __device__ __forceinline__ float sel_unkey(uint32_t key, uint32_t desc) { return tri_key_score(key, desc); }
 
-// A candidate source: segments.  Dense segment: scores[i], id = ids ? ids[i] : id_base + i.
-// Pair segment (pairs != 0): scores points at (score bits, position) pairs, id = ids[position].
+// Candidate source of one query: pair segments [0, nps) inside the candidate buffer -- (score bits,
+// position) pairs, id = ids[id_off + position] -- and at most one dense array (scores, with ids or, if
+// dense_ids is null, id = element number).
 struct SelSeg {
-    const float *scores;
+    uint32_t off;      // first pair of the segment (pair index into cand)
+    uint32_t len;      // pairs
+    uint32_t id_off;   // index of the list's first id in ids
+    uint32_t pfx;      // len summed over this and all earlier segments (cached descriptors only)
+};
+
+struct SelSrc {
+    const uint2 *cand;
     const uint32_t *ids;
-    uint32_t len;
-    uint32_t id_base;
-    uint32_t pairs;
-    uint32_t pad_;
+    const float *dense;
+    const uint32_t *dense_ids;
+    uint32_t nps;
+    uint32_t dense_len;
 };
 
 struct SelShared {
-    uint64_t pool[SEL_CAP];        // candidates / result (the sample's keys use its first half as uint32_t[SEL_CAP])
-    uint32_t hist[SEL_BINS];
-    SelSeg seg[SEL_SEGCACHE];      // descriptors of the first segments
+    uint64_t pool[SEL_CAP];        // candidates (the key sample uses it as uint32_t[2 * SEL_CAP])
+    union {
+        uint32_t hist[SEL_BINS];
+        uint64_t small[SEL_SMALL];
+    };
+    SelSeg seg[SEL_SEGCACHE];
     uint32_t wave_tot[8];
-    uint32_t digit, need, count, cnt;
+    uint32_t wmin[TRI_SEL_THREADS / 64], wmax[TRI_SEL_THREADS / 64];
+    uint32_t digit, need, count, cnt, tmax, total_pairs;
 };
 
-// `where` is what sel_for_each hands to its callback: the element's index (dense) or stored position (pairs)
-__device__ __forceinline__ uint32_t sel_id(const SelSeg &sg, uint32_t where) { return sg.ids ? sg.ids[where] : sg.id_base + where; }
+__device__ __forceinline__ uint32_t sel_id(const SelSrc &src, uint32_t idx, bool pair)
+{
+    return pair ? src.ids[idx] : (src.dense_ids ? src.dense_ids[idx] : idx);
+}
 
 // Inclusive scan of one value per thread across the workgroup (TRI_SEL_THREADS threads).
 __device__ __forceinline__ uint32_t sel_block_scan_incl(uint32_t v, uint32_t *wave_tot)
@@ -94,60 +117,122 @@ __device__ __forceinline__ void sel_find_digit(SelShared &sh, uint32_t nbins, ui
     __syncthreads();
 }
 
-// Enumerate candidates with wavefront-uniform control flow: f(valid, key, seg, pos) is called by all
-// 64 lanes together (valid = this lane has an element).  The segments are cut into chunks of
-// 64 * SEL_UNROLL elements and the workgroup's wavefronts take chunks round-robin across ALL
-// segments, so one long segment keeps every wavefront busy and many short ones are spread evenly;
-// the SEL_UNROLL loads of a chunk are issued together.  `stride` > 1 visits only the first
-// ceil(len / stride) elements of every segment (the sample: list order is id order, which carries no
-// information about the scores).  Segment descriptors come from the LDS cache filled by
-// sel_cache_segments, beyond it from seg_of.
-#define SEL_UNROLL 8
+// Descriptors of the first SEL_SEGCACHE pair segments -> LDS, with running sums of their lengths;
+// sh.total_pairs = pairs in ALL pair segments.  Ends with a barrier.
+template <class SegFn>
+__device__ __forceinline__ void sel_cache_segments(SelShared &sh, uint32_t nps, SegFn seg_of)
+{
+    const uint32_t ncache = nps < SEL_SEGCACHE ? nps : SEL_SEGCACHE;
+    const uint32_t per = (ncache + TRI_SEL_THREADS - 1) / TRI_SEL_THREADS;      // <= 3
+    const uint32_t s0 = threadIdx.x * per;
+    SelSeg mine[(SEL_SEGCACHE + TRI_SEL_THREADS - 1) / TRI_SEL_THREADS];
+    uint32_t sum = 0;
+#pragma unroll
+    for (uint32_t i = 0; i < (SEL_SEGCACHE + TRI_SEL_THREADS - 1) / TRI_SEL_THREADS; ++i)
+        if (i < per && s0 + i < ncache) {
+            mine[i] = seg_of(s0 + i);
+            sum += mine[i].len;
+        }
+    const uint32_t incl = sel_block_scan_incl(sum, sh.wave_tot);
+    uint32_t rest_incl = 0;                      // segments beyond the cache (very large probe counts only)
+    if (nps > SEL_SEGCACHE) {
+        uint32_t rest = 0;
+        for (uint32_t s = SEL_SEGCACHE + threadIdx.x; s < nps; s += TRI_SEL_THREADS) rest += seg_of(s).len;
+        rest_incl = sel_block_scan_incl(rest, sh.wave_tot);
+    }
+    uint32_t run = incl - sum;
+#pragma unroll
+    for (uint32_t i = 0; i < (SEL_SEGCACHE + TRI_SEL_THREADS - 1) / TRI_SEL_THREADS; ++i)
+        if (i < per && s0 + i < ncache) {
+            run += mine[i].len;
+            mine[i].pfx = run;
+            sh.seg[s0 + i] = mine[i];
+        }
+    if (threadIdx.x == TRI_SEL_THREADS - 1) sh.total_pairs = incl + rest_incl;
+    __syncthreads();
+}
 
+// Enumerate candidates with wavefront-uniform control flow: f(valid, key, idx, pair) is called by all
+// 64 lanes together (valid = this lane has an element; idx, pair: what sel_id needs).  Work is cut into
+// chunks of 64 * SEL_UNROLL elements that the wavefronts take round-robin, and the loads of a chunk are
+// issued together.
+//  * pair segments, all cached: ONE flat index space over all of them (a lane finds its segment by
+//    binary search in the running sums), so hundreds of segments of a dozen pairs cost no more than one
+//    long one.  stride > 1 visits every stride-th flat index.
+//  * pair segments beyond the cache: segment by segment (stride > 1: the first len/stride of each).
+//  * the dense array: stride > 1 visits its first ceil(len / stride) elements.
+// (The order of candidates inside the candidate buffer and of the centroids carries no information
+// about scores, which is what makes such subsets usable as samples.)
 template <class SegFn, class Fn>
-__device__ __forceinline__ void sel_for_each(const SelSeg *cache, uint32_t nseg, SegFn seg_of, uint32_t desc,
+__device__ __forceinline__ void sel_for_each(const SelShared &sh, const SelSrc &src, SegFn seg_of, uint32_t desc,
                                              uint32_t stride, Fn f)
 {
     const uint32_t lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     constexpr uint32_t CH = 64 * SEL_UNROLL;
-    uint32_t next = wave, base = 0;
-    for (uint32_t s = 0; s < nseg; ++s) {
-        const SelSeg sg = s < SEL_SEGCACHE ? cache[s] : seg_of(s);
-        const uint32_t n = stride > 1 ? (sg.len + stride - 1) / stride : sg.len;
-        const uint32_t nch = (n + CH - 1) / CH;
-        while (next < base + nch) {
-            const uint32_t i0 = (next - base) * CH + lane;
-            if (sg.pairs) {
-                const uint2 *pp = (const uint2 *)sg.scores;
+    constexpr uint32_t NW = TRI_SEL_THREADS / 64;
+    if (src.nps && src.nps <= SEL_SEGCACHE) {
+        const uint32_t nps = src.nps;
+        const uint32_t nvis = (sh.total_pairs + stride - 1) / stride;
+        uint32_t top = 1;
+        while (top * 2 <= nps) top *= 2;
+        for (uint32_t i0 = wave * CH; i0 < nvis; i0 += NW * CH) {
+            uint2 v[SEL_UNROLL];
+            uint32_t idx[SEL_UNROLL];
+#pragma unroll
+            for (int u = 0; u < SEL_UNROLL; ++u) {
+                const uint32_t i = i0 + u * 64 + lane;
+                const uint32_t e = i < nvis ? i * stride : 0u;
+                uint32_t lo = 0;                                 // segments whose running sum is <= e
+                for (uint32_t step = top; step > 0; step >>= 1) {
+                    const uint32_t m = lo + step;
+                    if (m <= nps && sh.seg[m - 1].pfx <= e) lo = m;
+                }
+                const SelSeg sg = sh.seg[lo < nps ? lo : nps - 1];
+                const uint32_t within = e - (sg.pfx - sg.len);
+                v[u] = i < nvis ? src.cand[(size_t)sg.off + within] : make_uint2(0u, 0u);
+                idx[u] = sg.id_off;
+            }
+#pragma unroll
+            for (int u = 0; u < SEL_UNROLL; ++u) {
+                const bool valid = i0 + u * 64 + lane < nvis;
+                f(valid, valid ? sel_key(__uint_as_float(v[u].x), desc) : 0xFFFFFFFFu, idx[u] + v[u].y, true);
+            }
+        }
+    } else if (src.nps) {
+        uint32_t next = wave, base = 0;
+        for (uint32_t s = 0; s < src.nps; ++s) {
+            const SelSeg sg = s < SEL_SEGCACHE ? sh.seg[s] : seg_of(s);
+            const uint32_t n = stride > 1 ? (sg.len + stride - 1) / stride : sg.len;
+            const uint32_t nch = (n + CH - 1) / CH;
+            while (next < base + nch) {
+                const uint32_t i0 = (next - base) * CH + lane;
                 uint2 v[SEL_UNROLL];
 #pragma unroll
-                for (int u = 0; u < SEL_UNROLL; ++u) v[u] = i0 + u * 64 < n ? pp[i0 + u * 64] : make_uint2(0u, 0u);
+                for (int u = 0; u < SEL_UNROLL; ++u)
+                    v[u] = i0 + u * 64 < n ? src.cand[(size_t)sg.off + i0 + u * 64] : make_uint2(0u, 0u);
 #pragma unroll
                 for (int u = 0; u < SEL_UNROLL; ++u) {
                     const bool valid = i0 + u * 64 < n;
-                    f(valid, valid ? sel_key(__uint_as_float(v[u].x), desc) : 0xFFFFFFFFu, sg, v[u].y);
+                    f(valid, valid ? sel_key(__uint_as_float(v[u].x), desc) : 0xFFFFFFFFu, sg.id_off + v[u].y, true);
                 }
-            } else {
-                float v[SEL_UNROLL];
-#pragma unroll
-                for (int u = 0; u < SEL_UNROLL; ++u) v[u] = i0 + u * 64 < n ? sg.scores[i0 + u * 64] : 0.f;
-#pragma unroll
-                for (int u = 0; u < SEL_UNROLL; ++u) {
-                    const bool valid = i0 + u * 64 < n;
-                    f(valid, valid ? sel_key(v[u], desc) : 0xFFFFFFFFu, sg, i0 + u * 64);
-                }
+                next += NW;
             }
-            next += TRI_SEL_THREADS / 64;
+            base += nch;
         }
-        base += nch;
     }
-}
-
-template <class SegFn>
-__device__ __forceinline__ void sel_cache_segments(SelSeg *cache, uint32_t nseg, SegFn seg_of)
-{
-    for (uint32_t s = threadIdx.x; s < nseg && s < SEL_SEGCACHE; s += TRI_SEL_THREADS) cache[s] = seg_of(s);
-    __syncthreads();
+    if (src.dense_len) {
+        const uint32_t n = stride > 1 ? (src.dense_len + stride - 1) / stride : src.dense_len;
+        for (uint32_t i0 = wave * CH; i0 < n; i0 += NW * CH) {
+            float v[SEL_UNROLL];
+#pragma unroll
+            for (int u = 0; u < SEL_UNROLL; ++u) v[u] = i0 + u * 64 + lane < n ? src.dense[i0 + u * 64 + lane] : 0.f;
+#pragma unroll
+            for (int u = 0; u < SEL_UNROLL; ++u) {
+                const bool valid = i0 + u * 64 + lane < n;
+                f(valid, valid ? sel_key(v[u], desc) : 0xFFFFFFFFu, i0 + u * 64 + lane, false);
+            }
+        }
+    }
 }
 
 // Append slot for every lane with pred set: one LDS atomic per wavefront call, not per lane.
@@ -189,9 +274,147 @@ __device__ __forceinline__ void sel_bitonic(T *a, uint32_t n)
     }
 }
 
-// Path (3): exact radix select of the k best into sh.pool[0..k), unsorted.  total > k.
+// ---- buckets ------------------------------------------------------------------------------------
+__device__ __forceinline__ uint32_t sel_key_of(uint32_t x) { return x; }
+__device__ __forceinline__ uint32_t sel_key_of(uint64_t x) { return (uint32_t)(x >> 32); }
+
+// Bucket of a key: monotone in the key (conversions, the product with a positive factor and the
+// truncation all preserve order), 0 at or below kmin, SEL_BINS - 1 at or above kmax.
+__device__ __forceinline__ uint32_t sel_bucket(uint32_t key, uint32_t kmin, float scale)
+{
+    if (key <= kmin) return 0u;
+    return (uint32_t)fminf((float)(key - kmin) * scale, (float)(SEL_BINS - 1));
+}
+
+// Smallest and largest key among a[0..n) (keys equal to all-ones, the padding value, are ignored) and
+// a zeroed histogram.  Ends with a barrier.  Returns the scale of sel_bucket.
+template <typename T>
+__device__ __forceinline__ float sel_range(SelShared &sh, const T *a, uint32_t n, uint32_t &kmin)
+{
+    const uint32_t lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    uint32_t lo = 0xFFFFFFFFu, hi = 0u;
+    for (uint32_t i = threadIdx.x; i < n; i += TRI_SEL_THREADS) {
+        const uint32_t key = sel_key_of(a[i]);
+        if (key != 0xFFFFFFFFu) {
+            lo = key < lo ? key : lo;
+            hi = key > hi ? key : hi;
+        }
+    }
+#pragma unroll
+    for (int d = 32; d > 0; d >>= 1) {
+        const uint32_t l2 = (uint32_t)__shfl_xor((int)lo, d, 64), h2 = (uint32_t)__shfl_xor((int)hi, d, 64);
+        lo = l2 < lo ? l2 : lo;
+        hi = h2 > hi ? h2 : hi;
+    }
+    if (lane == 0) {
+        sh.wmin[wave] = lo;
+        sh.wmax[wave] = hi;
+    }
+    for (uint32_t i = threadIdx.x; i < SEL_BINS; i += TRI_SEL_THREADS) sh.hist[i] = 0;
+    __syncthreads();
+#pragma unroll
+    for (uint32_t w = 0; w < TRI_SEL_THREADS / 64; ++w) {
+        lo = sh.wmin[w] < lo ? sh.wmin[w] : lo;
+        hi = sh.wmax[w] > hi ? sh.wmax[w] : hi;
+    }
+    kmin = lo;
+    return hi > lo ? ((float)SEL_BINS - 0.01f) / (float)(hi - lo) : 0.f;
+}
+
+// A key T with at least m of the n keys a[0..n) not above it, and few more (a: LDS, n >= m >= 1 keys of
+// which at least m are not the padding value all-ones).  Uses sh.hist.
+__device__ uint32_t sel_keys_threshold(SelShared &sh, const uint32_t *a, uint32_t n, uint32_t m)
+{
+    uint32_t kmin;
+    const float scale = sel_range(sh, a, n, kmin);
+    for (uint32_t i = threadIdx.x; i < n; i += TRI_SEL_THREADS) atomicAdd(&sh.hist[sel_bucket(a[i], kmin, scale)], 1u);
+    if (threadIdx.x == 0) sh.tmax = 0u;
+    __syncthreads();
+    sel_find_digit(sh, SEL_BINS, m);
+    const uint32_t B = sh.digit;
+    uint32_t best = 0;
+    for (uint32_t i = threadIdx.x; i < n; i += TRI_SEL_THREADS) {
+        const uint32_t key = a[i];
+        if (sel_bucket(key, kmin, scale) == B && key > best) best = key;
+    }
+#pragma unroll
+    for (int d = 32; d > 0; d >>= 1) {
+        const uint32_t b2 = (uint32_t)__shfl_xor((int)best, d, 64);
+        best = b2 > best ? b2 : best;
+    }
+    if ((threadIdx.x & 63) == 0) atomicMax(&sh.tmax, best);
+    __syncthreads();
+    const uint32_t t = sh.tmax;
+    __syncthreads();                     // (sh.tmax and the histogram may be reused right away)
+    return t;
+}
+
+// Sort m <= SEL_RANK_MAX composites by counting, src -> dst (both LDS, distinct): the thread that owns an
+// element counts the elements ordered before it and writes it to that place.  Every thread of a
+// wavefront reads the same address in each round (a broadcast).  Ends with a barrier.
+__device__ __forceinline__ void sel_rank_sort(const uint64_t *src, uint32_t m, uint64_t *dst)
+{
+    const uint32_t t = threadIdx.x;
+    const uint64_t x = t < m ? src[t] : ~0ull;
+    uint32_t rank = 0;
+    uint32_t u = 0;
+    for (; u + 4 <= m; u += 4) {
+        const uint64_t y0 = src[u], y1 = src[u + 1], y2 = src[u + 2], y3 = src[u + 3];
+        rank += (y0 < x || (y0 == x && u < t)) + (y1 < x || (y1 == x && u + 1 < t)) +
+                (y2 < x || (y2 == x && u + 2 < t)) + (y3 < x || (y3 == x && u + 3 < t));
+    }
+    for (; u < m; ++u) {
+        const uint64_t y = src[u];
+        rank += (y < x || (y == x && u < t));
+    }
+    if (t < m) dst[rank] = x;
+    __syncthreads();
+}
+
+// The k best of the n <= SEL_CAP composites in sh.pool[0..n), sorted ascending; returns where they are
+// (sh.pool or sh.small).  All threads must call it with everything in sh.pool visible (after a barrier);
+// it ends with a barrier.
+__device__ const uint64_t *sel_pool_topk(SelShared &sh, uint32_t n, uint32_t k)
+{
+    if (n <= SEL_RANK_MAX) {
+        sel_rank_sort(sh.pool, n, sh.small);
+        return sh.small;
+    }
+    if (k < n && k < SEL_SMALL) {
+        uint32_t kmin;
+        const float scale = sel_range(sh, sh.pool, n, kmin);
+        for (uint32_t i = threadIdx.x; i < n; i += TRI_SEL_THREADS)
+            atomicAdd(&sh.hist[sel_bucket(sel_key_of(sh.pool[i]), kmin, scale)], 1u);
+        if (threadIdx.x == 0) sh.cnt = 0;
+        __syncthreads();
+        sel_find_digit(sh, SEL_BINS, k);
+        const uint32_t B = sh.digit;
+        const uint32_t c_le = k - sh.need + sh.count;        // elements in buckets <= B
+        __syncthreads();                                      // the histogram is dead from here: sh.small reuses it
+        if (c_le <= SEL_SMALL) {
+            for (uint32_t i0 = 0; i0 < n; i0 += TRI_SEL_THREADS) {
+                const uint32_t i = i0 + threadIdx.x;
+                const uint64_t x = i < n ? sh.pool[i] : ~0ull;
+                const bool take = i < n && sel_bucket(sel_key_of(x), kmin, scale) <= B;
+                const uint32_t pos = sel_append_pos(take, &sh.cnt);
+                if (take) sh.small[pos] = x;
+            }
+            __syncthreads();
+            if (c_le <= SEL_RANK_MAX) {
+                sel_rank_sort(sh.small, c_le, sh.pool);
+                return sh.pool;
+            }
+            sel_bitonic(sh.small, c_le);
+            return sh.small;
+        }
+    }
+    sel_bitonic(sh.pool, n);
+    return sh.pool;
+}
+
+// Exact radix select of the k best into sh.pool[0..k), unsorted.  total > k.
 template <class SegFn>
-__device__ void sel_radix(SelShared &sh, uint32_t nseg, SegFn seg_of, uint32_t k, uint32_t desc)
+__device__ void sel_radix(SelShared &sh, const SelSrc &src, SegFn seg_of, uint32_t k, uint32_t desc)
 {
     const uint32_t tid = threadIdx.x;
     uint32_t T = 0, Tid = 0xFFFFFFFFu;
@@ -202,7 +425,7 @@ __device__ void sel_radix(SelShared &sh, uint32_t nseg, SegFn seg_of, uint32_t k
         for (uint32_t i = tid; i < SEL_BINS; i += TRI_SEL_THREADS) sh.hist[i] = 0;
         __syncthreads();
         const uint32_t hi_shift = shift + width;
-        sel_for_each(sh.seg, nseg, seg_of, desc, 1u, [&](bool valid, uint32_t key, const SelSeg &, uint32_t) {
+        sel_for_each(sh, src, seg_of, desc, 1u, [&](bool valid, uint32_t key, uint32_t, bool) {
             if (valid && (pass == 0 || (key >> hi_shift) == prefix)) atomicAdd(&sh.hist[(key >> shift) & (nb - 1)], 1u);
         });
         __syncthreads();
@@ -221,9 +444,9 @@ __device__ void sel_radix(SelShared &sh, uint32_t nseg, SegFn seg_of, uint32_t k
             for (uint32_t i = tid; i < SEL_BINS; i += TRI_SEL_THREADS) sh.hist[i] = 0;
             __syncthreads();
             const uint32_t hi_shift = shift + width;
-            sel_for_each(sh.seg, nseg, seg_of, desc, 1u, [&](bool valid, uint32_t key, const SelSeg &sg, uint32_t i) {
+            sel_for_each(sh, src, seg_of, desc, 1u, [&](bool valid, uint32_t key, uint32_t idx, bool pair) {
                 if (!valid || key != T) return;
-                const uint32_t id = sel_id(sg, i);
+                const uint32_t id = sel_id(src, idx, pair);
                 if (pass == 0 || (id >> hi_shift) == idprefix) atomicAdd(&sh.hist[(id >> shift) & (nb - 1)], 1u);
             });
             __syncthreads();
@@ -236,11 +459,11 @@ __device__ void sel_radix(SelShared &sh, uint32_t nseg, SegFn seg_of, uint32_t k
     }
     if (tid == 0) sh.cnt = 0;
     __syncthreads();
-    sel_for_each(sh.seg, nseg, seg_of, desc, 1u, [&](bool valid, uint32_t key, const SelSeg &sg, uint32_t i) {
+    sel_for_each(sh, src, seg_of, desc, 1u, [&](bool valid, uint32_t key, uint32_t idx, bool pair) {
         bool take = valid && key <= T;
         uint32_t id = 0;
         if (take) {
-            id = sel_id(sg, i);
+            id = sel_id(src, idx, pair);
             take = key < T || id <= Tid;
         }
         const uint32_t pos = sel_append_pos(take, &sh.cnt);
@@ -249,67 +472,64 @@ __device__ void sel_radix(SelShared &sh, uint32_t nseg, SegFn seg_of, uint32_t k
     __syncthreads();
 }
 
-// Select the k best of `total` candidates into sh.pool[0..n) sorted ascending by (key, id).
-// Returns n = min(k, total).  All threads of the workgroup must call it; it ends with a barrier.
+// Select the k best candidates of src, sorted ascending by (key, id); *n_out = min(k, total).  Returns
+// where they are in LDS.  All threads of the workgroup must call it; it ends with a barrier.
 template <class SegFn>
-__device__ uint32_t sel_block_topk(SelShared &sh, uint32_t nseg, SegFn seg_of, uint32_t total, uint32_t k,
-                                   uint32_t desc)
+__device__ const uint64_t *sel_block_topk(SelShared &sh, const SelSrc &src, SegFn seg_of, uint32_t k, uint32_t desc,
+                                          uint32_t *n_out)
 {
     const uint32_t tid = threadIdx.x;
-    const uint32_t n = total < k ? total : k;
-    sel_cache_segments(sh.seg, nseg, seg_of);
-    if (total <= SEL_CAP) {
-        // ---- (1) everything fits
-        if (tid == 0) sh.cnt = 0;
-        __syncthreads();
-        sel_for_each(sh.seg, nseg, seg_of, desc, 1u, [&](bool valid, uint32_t key, const SelSeg &sg, uint32_t i) {
-            const uint32_t pos = sel_append_pos(valid, &sh.cnt);
-            if (valid) sh.pool[pos] = ((uint64_t)key << 32) | sel_id(sg, i);
-        });
-        __syncthreads();
-        sel_bitonic(sh.pool, total);
-        return n;
-    }
-    // ---- (2) threshold from a sorted sample
-    uint32_t *skeys = (uint32_t *)sh.pool;
-    const uint32_t stride = (total + SEL_SAMPLE - 1) / SEL_SAMPLE;
+    sel_cache_segments(sh, src.nps, seg_of);
+    const uint32_t total = sh.total_pairs + src.dense_len;
+    *n_out = total < k ? total : k;
     if (tid == 0) sh.cnt = 0;
     __syncthreads();
-    sel_for_each(sh.seg, nseg, seg_of, desc, stride, [&](bool valid, uint32_t key, const SelSeg &, uint32_t) {
+    if (total <= SEL_CAP) {
+        // ---- everything fits
+        sel_for_each(sh, src, seg_of, desc, 1u, [&](bool valid, uint32_t key, uint32_t idx, bool pair) {
+            const uint32_t pos = sel_append_pos(valid, &sh.cnt);
+            if (valid) sh.pool[pos] = ((uint64_t)key << 32) | sel_id(src, idx, pair);
+        });
+        __syncthreads();
+        return sel_pool_topk(sh, total, k);
+    }
+    // ---- threshold from a sample
+    uint32_t *skeys = (uint32_t *)sh.pool;
+    const uint32_t stride = (total + SEL_SAMPLE - 1) / SEL_SAMPLE;
+    sel_for_each(sh, src, seg_of, desc, stride, [&](bool valid, uint32_t key, uint32_t, bool) {
         const uint32_t pos = sel_append_pos(valid, &sh.cnt);
-        if (valid && pos < SEL_CAP) skeys[pos] = key;      // (a few sample keys too many are simply dropped)
+        if (valid && pos < 2 * SEL_CAP) skeys[pos] = key;      // (a few sample keys too many are simply dropped)
     });
     __syncthreads();
-    const uint32_t ns = sh.cnt < SEL_CAP ? sh.cnt : SEL_CAP;
-    sel_bitonic(skeys, ns);
+    const uint32_t ns = sh.cnt < 2 * SEL_CAP ? sh.cnt : 2 * SEL_CAP;
     // expected rank of the k-th best inside the sample, plus five standard deviations and a floor
     const float mu = (float)k * (float)ns / (float)total;
     const uint32_t m = (uint32_t)(mu + 5.0f * sqrtf(mu) + 4.0f);
     bool done = false;
+    const uint64_t *res = sh.pool;
     if (m < ns) {
-        const uint32_t t0 = skeys[m];
-        __syncthreads();                       // everyone has read the threshold before the pool is reused
+        const uint32_t t0 = sel_keys_threshold(sh, skeys, ns, m + 1);
         if (tid == 0) sh.cnt = 0;
         __syncthreads();
-        sel_for_each(sh.seg, nseg, seg_of, desc, 1u, [&](bool valid, uint32_t key, const SelSeg &sg, uint32_t i) {
+        sel_for_each(sh, src, seg_of, desc, 1u, [&](bool valid, uint32_t key, uint32_t idx, bool pair) {
             const bool take = valid && key <= t0;
             const uint32_t pos = sel_append_pos(take, &sh.cnt);
-            if (take && pos < SEL_CAP) sh.pool[pos] = ((uint64_t)key << 32) | sel_id(sg, i);
+            if (take && pos < SEL_CAP) sh.pool[pos] = ((uint64_t)key << 32) | sel_id(src, idx, pair);
         });
         __syncthreads();
         const uint32_t c = sh.cnt;
         if (c >= k && c <= SEL_CAP) {
-            sel_bitonic(sh.pool, c);
+            res = sel_pool_topk(sh, c, k);
             done = true;
         }
     }
     __syncthreads();
     if (!done) {
-        // ---- (3) exact radix select, then sort the k survivors
-        sel_radix(sh, nseg, seg_of, k, desc);
-        sel_bitonic(sh.pool, k);
+        // ---- exact radix select, then sort the k survivors
+        sel_radix(sh, src, seg_of, k, desc);
+        res = sel_pool_topk(sh, k, k);
     }
-    return n;
+    return res;
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -321,11 +541,12 @@ __global__ __launch_bounds__(TRI_SEL_THREADS) void coarse_select_kernel(
 {
     __shared__ SelShared sh;
     const TriNewDesc d = desc[first_new + blockIdx.x];
-    const float *row = scores + (size_t)blockIdx.x * ldc;
-    auto seg_of = [&](uint32_t) { return SelSeg{row, nullptr, nlist, 0u, 0u, 0u}; };
-    const uint32_t n = sel_block_topk(sh, 1u, seg_of, nlist, d.nprobe, d.metric);
+    const SelSrc src = {nullptr, nullptr, scores + (size_t)blockIdx.x * ldc, nullptr, 0u, nlist};
+    auto seg_of = [&](uint32_t) { return SelSeg{0u, 0u, 0u, 0u}; };
+    uint32_t n;
+    const uint64_t *best = sel_block_topk(sh, src, seg_of, d.nprobe, d.metric, &n);
     uint32_t *dst = probe + (size_t)d.slot * nprobe_max;
-    for (uint32_t i = threadIdx.x; i < n; i += TRI_SEL_THREADS) dst[i] = (uint32_t)(sh.pool[i] & 0xFFFFFFFFu);
+    for (uint32_t i = threadIdx.x; i < n; i += TRI_SEL_THREADS) dst[i] = (uint32_t)(best[i] & 0xFFFFFFFFu);
 }
 
 hipError_t tri_launch_coarse_select(const TriLaunchCtx &c, const TriDevWs &ws, const TriNewDesc *desc_dev,
@@ -338,10 +559,10 @@ hipError_t tri_launch_coarse_select(const TriLaunchCtx &c, const TriDevWs &ws, c
 }
 
 // ------------------------------------------------------------------------------------------------
-// Threshold of each running slot for this step's scan: the k-th best key among the slot's sample
-// scores (the first TRI_SAMPLE_VECS vectors of up to TRI_THRESH_ITEMS of its lists) and its running
-// top-k -- a subset of its candidates, so nothing of its final top-k lies beyond it.  Fewer than k
-// such keys: no filtering (all-ones).
+// Threshold of each running slot for this step's scan: a bound for the k-th best key among the slot's
+// sample scores (the first TRI_SAMPLE_VECS vectors of up to TRI_THRESH_ITEMS of its lists) and its
+// running top-k -- a subset of its candidates, so nothing of its final top-k lies beyond it.  Fewer
+// than k such keys: no filtering (all-ones).
 __global__ __launch_bounds__(TRI_SEL_THREADS) void slot_threshold_kernel(
     const TriPlanEntry *__restrict__ plan, const TriSlotMeta *__restrict__ slot_meta,
     const uint32_t *__restrict__ item_glist, const uint32_t *__restrict__ item_sorted_pos,
@@ -356,31 +577,35 @@ __global__ __launch_bounds__(TRI_SEL_THREADS) void slot_threshold_kernel(
     const uint32_t have = e.cursor > 0 ? topk_count[e.slot] : 0u;
     const uint32_t nitems = e.take < TRI_THRESH_ITEMS ? e.take : TRI_THRESH_ITEMS;
     uint32_t *keys = (uint32_t *)sh.pool;                  // room for 2 * SEL_CAP keys
+    // per item: where its sample row is and how many of its TRI_SAMPLE_VECS scores exist
+    uint32_t *row_of = sh.hist, *len_of = sh.hist + TRI_THRESH_ITEMS;
     if (threadIdx.x == 0) sh.cnt = 0;
-    __syncthreads();
-    // wavefronts take items round-robin; lanes 0..31 the item's sample row
-    const uint32_t lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    for (uint32_t s = wave; s < nitems; s += TRI_SEL_THREADS / 64) {
+    for (uint32_t s = threadIdx.x; s < nitems; s += TRI_SEL_THREADS) {
         const uint32_t it = e.item_base + s;
-        const uint32_t n = min(glist_len[item_glist[it]], (uint32_t)TRI_SAMPLE_VECS);
-        const bool valid = lane < n;
-        const float v = valid ? sample_scores[(size_t)item_sorted_pos[it] * TRI_SAMPLE_VECS + lane] : 0.f;
-        const uint32_t pos = sel_append_pos(valid, &sh.cnt);
-        if (valid) keys[pos] = sel_key(v, desc);
-    }
-    for (uint32_t i0 = wave * 64; i0 < have; i0 += TRI_SEL_THREADS) {
-        const bool valid = i0 + lane < have;
-        const float v = valid ? topk_score[(size_t)e.slot * kmax + i0 + lane] : 0.f;
-        const uint32_t pos = sel_append_pos(valid, &sh.cnt);
-        if (valid) keys[pos] = sel_key(v, desc);
+        row_of[s] = item_sorted_pos[it];
+        len_of[s] = min(glist_len[item_glist[it]], (uint32_t)TRI_SAMPLE_VECS);
     }
     __syncthreads();
-    const uint32_t n = sh.cnt;                             // <= 96 * 32 + 1024 = SEL_CAP
-    uint32_t thr = 0xFFFFFFFFu;
-    if (n >= meta.k) {
-        sel_bitonic(keys, n);
-        thr = keys[meta.k - 1];
+    // keys[s * 32 + l] = key of sample l of item s (all-ones where the list is shorter), then the running top-k
+    const uint32_t nsample = nitems * TRI_SAMPLE_VECS, n = nsample + have;
+    uint32_t valid_here = 0;
+    for (uint32_t i = threadIdx.x; i < n; i += TRI_SEL_THREADS) {
+        uint32_t key = 0xFFFFFFFFu;
+        if (i < nsample) {
+            const uint32_t s = i / TRI_SAMPLE_VECS, l = i % TRI_SAMPLE_VECS;
+            if (l < len_of[s]) key = sel_key(sample_scores[(size_t)row_of[s] * TRI_SAMPLE_VECS + l], desc);
+        } else {
+            key = sel_key(topk_score[(size_t)e.slot * kmax + (i - nsample)], desc);
+        }
+        keys[i] = key;
+        valid_here += key != 0xFFFFFFFFu;
     }
+    if (valid_here) atomicAdd(&sh.cnt, valid_here);
+    __syncthreads();
+    const uint32_t nvalid = sh.cnt;
+    __syncthreads();
+    uint32_t thr = 0xFFFFFFFFu;
+    if (nvalid >= meta.k) thr = sel_keys_threshold(sh, keys, n, meta.k);
     if (threadIdx.x == 0) thr_key[e.slot] = thr;
 }
 
@@ -402,62 +627,49 @@ __global__ __launch_bounds__(TRI_SEL_THREADS) void slot_merge_kernel(
     const TriIndexDev *__restrict__ indexes, const uint32_t *__restrict__ item_glist,
     const uint64_t *__restrict__ item_score_off, const uint32_t *__restrict__ item_sorted_pos,
     const uint32_t *__restrict__ surv_count, uint32_t chunk_vecs, const uint32_t *__restrict__ glist_len,
-    const uint32_t *__restrict__ glist_voff, const uint32_t *__restrict__ glist_index,
-    const float *__restrict__ cand, float *__restrict__ topk_score, uint32_t *__restrict__ topk_id,
-    uint32_t *__restrict__ topk_count, uint32_t kmax, uint32_t *__restrict__ res_block,
-    const uint32_t *__restrict__ probe, uint32_t nprobe_max, uint32_t *__restrict__ res_probes)
+    const uint32_t *__restrict__ glist_voff, const float *__restrict__ cand, float *__restrict__ topk_score,
+    uint32_t *__restrict__ topk_id, uint32_t *__restrict__ topk_count, uint32_t kmax,
+    uint32_t *__restrict__ res_block, const uint32_t *__restrict__ probe, uint32_t nprobe_max,
+    uint32_t *__restrict__ res_probes)
 {
     __shared__ SelShared sh;
-    __shared__ uint32_t sh_total;
     const TriPlanEntry e = plan[blockIdx.x];
     const TriSlotMeta meta = slot_meta[e.slot];
     const uint32_t desc = meta.metric == 1u;
     const uint32_t have = e.cursor > 0 ? topk_count[e.slot] : 0u;
     float *run_score = topk_score + (size_t)e.slot * kmax;
     uint32_t *run_id = topk_id + (size_t)e.slot * kmax;
-    const uint32_t nlist_seg = e.take * TRI_TILES_PER_ITEM;
-    const uint32_t nseg = nlist_seg + (have ? 1u : 0u);
+    const SelSrc src = {(const uint2 *)cand, indexes[meta.index].ids, run_score, run_id,
+                        e.take * TRI_TILES_PER_ITEM, have};
 
-    // segment s < nlist_seg: chunk s % 4 of item s / 4 (empty when the list has fewer chunks)
+    // pair segment s: chunk s % 4 of item s / 4 (empty when the list has fewer chunks)
     auto seg_of = [&](uint32_t s) {
-        if (s < nlist_seg) {
-            const uint32_t it = e.item_base + s / TRI_TILES_PER_ITEM, ch = s % TRI_TILES_PER_ITEM;
-            const uint32_t g = item_glist[it];
-            const uint32_t nch = (glist_len[g] + chunk_vecs - 1) / chunk_vecs;
-            if (ch >= nch) return SelSeg{cand, nullptr, 0u, 0u, 1u, 0u};
-            const TriIndexDev &ix = indexes[glist_index[g]];
-            return SelSeg{cand + item_score_off[it] + 2u * (size_t)ch * chunk_vecs, ix.ids + glist_voff[g],
-                          surv_count[item_sorted_pos[it] * TRI_TILES_PER_ITEM + ch], 0u, 1u, 0u};
-        }
-        return SelSeg{run_score, run_id, have, 0u, 0u, 0u};
+        const uint32_t it = e.item_base + s / TRI_TILES_PER_ITEM, ch = s % TRI_TILES_PER_ITEM;
+        const uint32_t g = item_glist[it];
+        const uint32_t nch = (glist_len[g] + chunk_vecs - 1) / chunk_vecs;
+        if (ch >= nch) return SelSeg{0u, 0u, 0u, 0u};
+        return SelSeg{(uint32_t)(item_score_off[it] / 2u) + ch * chunk_vecs,
+                      surv_count[item_sorted_pos[it] * TRI_TILES_PER_ITEM + ch], glist_voff[g], 0u};
     };
-    // total number of candidates
-    if (threadIdx.x == 0) sh_total = have;
-    __syncthreads();
-    uint32_t part = 0;
-    for (uint32_t s = threadIdx.x; s < nlist_seg; s += TRI_SEL_THREADS) part += seg_of(s).len;
-    if (part) atomicAdd(&sh_total, part);
-    __syncthreads();
-    const uint32_t total = sh_total;
-
-    const uint32_t n = sel_block_topk(sh, nseg, seg_of, total, meta.k, desc);
+    uint32_t n;
+    const uint64_t *best = sel_block_topk(sh, src, seg_of, meta.k, desc, &n);
     // (all reads of the running buffer are done: sel_block_topk ends with a barrier)
     if (e.retire_idx >= 0) {
         uint32_t *rec = res_block + (size_t)e.retire_idx * (1u + 2u * kmax);
         if (threadIdx.x == 0) rec[0] = n;
         for (uint32_t i = threadIdx.x; i < n; i += TRI_SEL_THREADS) {
-            const uint64_t c = sh.pool[i];
+            const uint64_t c = best[i];
             rec[1 + i] = (uint32_t)(c & 0xFFFFFFFFu);
             rec[1 + kmax + i] = __float_as_uint(sel_unkey((uint32_t)(c >> 32), desc));
         }
         if (res_probes) {
-            const uint32_t *src = probe + (size_t)e.slot * nprobe_max;
+            const uint32_t *srcp = probe + (size_t)e.slot * nprobe_max;
             uint32_t *dst = res_probes + (size_t)e.retire_idx * nprobe_max;
-            for (uint32_t i = threadIdx.x; i < meta.nprobe; i += TRI_SEL_THREADS) dst[i] = src[i];
+            for (uint32_t i = threadIdx.x; i < meta.nprobe; i += TRI_SEL_THREADS) dst[i] = srcp[i];
         }
     } else {
         for (uint32_t i = threadIdx.x; i < n; i += TRI_SEL_THREADS) {
-            const uint64_t c = sh.pool[i];
+            const uint64_t c = best[i];
             run_id[i] = (uint32_t)(c & 0xFFFFFFFFu);
             run_score[i] = sel_unkey((uint32_t)(c >> 32), desc);
         }
@@ -471,7 +683,7 @@ hipError_t tri_launch_merge(const TriLaunchCtx &c, const TriDevWs &ws, const Tri
     if (n_plan == 0) return hipSuccess;
     hipLaunchKernelGGL(slot_merge_kernel, dim3(n_plan), dim3(TRI_SEL_THREADS), 0, c.stream, plan_dev, ws.slot_meta,
                        ws.indexes, ws.item_glist, ws.item_score_off, ws.item_sorted_pos, ws.surv_count, chunk_vecs,
-                       ws.glist_len, ws.glist_voff, ws.glist_index, ws.scores, ws.topk_score, ws.topk_id, ws.topk_count,
-                       c.kmax, ws.res_block, ws.probe, c.nprobe_max, keep_probes ? ws.res_probes : (uint32_t *)nullptr);
+                       ws.glist_len, ws.glist_voff, ws.scores, ws.topk_score, ws.topk_id, ws.topk_count, c.kmax,
+                       ws.res_block, ws.probe, c.nprobe_max, keep_probes ? ws.res_probes : (uint32_t *)nullptr);
     return hipGetLastError();
 }

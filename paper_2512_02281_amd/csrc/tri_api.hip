@@ -210,6 +210,8 @@ int derive(const tri_pool_cfg *c, uint32_t *max_row_bytes, uint32_t *coarse_rows
     if (*coarse_rows > c->slots) *coarse_rows = c->slots;
     *coarse_ldc = round_up(c->max_nlist, 32u);
     *score_capacity = c->score_capacity ? c->score_capacity : (uint64_t)c->items_per_step * 2048u;
+    if (*score_capacity > (1ull << 32))      // candidate pairs are addressed with 32-bit pair numbers
+        return fail(TRI_EINVAL, "score_capacity must not exceed 2^32 words");
     *upload_bytes = round_up_sz((size_t)c->slots * sizeof(TriNewDesc), 256) +
                     round_up_sz((size_t)c->slots * sizeof(TriPlanEntry), 256) + (size_t)c->slots * *max_row_bytes;
     return TRI_OK;
