@@ -208,6 +208,32 @@ int search_cancel(tri_pool *pool, tri_ticket t);
 /* Block until all enqueued steps have completed and their results are pollable. */
 int search_sync(tri_pool *pool);
 
+/* The serving loop of Sec. 3.2 ("new arrivals are admitted and contribute tasks to the next batch ...
+ * completed requests exit immediately") as one native call, for measuring a stream: query i is
+ * queued when arrival_s[i] seconds have passed since the call began (its vector is copied then), a
+ * step is enqueued whenever there is work and fewer than `depth` steps are in flight (0 = 2; at most
+ * 4) -- never waiting for a batch to fill --, and every result is stored as soon as its step has
+ * completed.  The pool must be idle when the call begins; it returns when all n queries are answered.
+ *  q, arrival_s [host] n: the queries (arrival times in seconds, not decreasing).
+ *  stride: entries per output row, >= every query's k.
+ *  n_out [host] n, ids / dist [host] n*stride: filled like search_poll fills them, row i for query i.
+ *  done_s [host] n: seconds from the beginning of the call until the result of query i was on the
+ *      host; latency of query i = done_s[i] - arrival_s[i].
+ *  probes [host] n*nprobe_max or NULL: the probe list of query i in row i (needs TRI_FLAG_KEEP_PROBES).
+ *  stats [host] out or NULL. */
+typedef struct {
+    double wall_s;         /* duration of the call                                                  */
+    uint64_t steps;        /* steps that scanned something                                          */
+    uint64_t items;        /* work items over those steps                                           */
+    uint64_t capacity;     /* W summed over those steps: 1 - items / capacity is the padding share   */
+    uint64_t running;      /* occupied slots summed over those steps                                */
+    uint64_t max_pending;  /* longest the two queues together ever were                             */
+} tri_stream_stats;
+int search_run_stream(tri_pool *pool, const tri_query *q /*[host] n*/, const double *arrival_s /*[host] n*/, uint32_t n,
+                      uint32_t depth, uint32_t stride, uint32_t *n_out /*[host] n*/, int64_t *ids /*[host] n*stride*/,
+                      float *dist /*[host] n*stride*/, double *done_s /*[host] n*/, uint32_t *probes /*[host] or NULL*/,
+                      tri_stream_stats *stats /*[host] out or NULL*/);
+
 /* Accumulated GPU time per kernel class since pool creation or the last reset (needs
  * TRI_FLAG_PROFILE; measured with HIP events on the pool's stream around each launch group). */
 typedef struct {

@@ -72,10 +72,15 @@ class tri_kernel_times(ctypes.Structure):
                 ("scan_unique_bytes", ctypes.c_uint64), ("scan_items", ctypes.c_uint64)]
 
 
+class tri_stream_stats(ctypes.Structure):
+    _fields_ = [("wall_s", ctypes.c_double), ("steps", ctypes.c_uint64), ("items", ctypes.c_uint64),
+                ("capacity", ctypes.c_uint64), ("running", ctypes.c_uint64), ("max_pending", ctypes.c_uint64)]
+
+
 EXPORTS = ["tri_pool_workspace_bytes", "tri_pool_create", "tri_pool_destroy", "ivf_build_bytes", "ivf_build",
            "ivf_export", "ivf_info", "ivf_destroy", "search_submit", "search_submit_batch", "search_submit_batch_dev",
            "search_step", "search_poll", "search_poll_batch", "search_probes", "search_cancel", "search_sync",
-           "tri_pool_kernel_times", "tri_last_error", "tri_version"]
+           "search_run_stream", "tri_pool_kernel_times", "tri_last_error", "tri_version"]
 
 
 def _load():
@@ -105,6 +110,7 @@ def _load():
     lib.search_probes.argtypes = [vp, u64, vp, P(u32)]
     lib.search_cancel.argtypes = [vp, u64]
     lib.search_sync.argtypes = [vp]
+    lib.search_run_stream.argtypes = [vp, vp, vp, u32, u32, u32, vp, vp, vp, vp, vp, P(tri_stream_stats)]
     lib.tri_pool_kernel_times.argtypes = [vp, P(tri_kernel_times), ctypes.c_int]
     lib.tri_last_error.restype = ctypes.c_char_p
     lib.tri_version.restype = ctypes.c_char_p
@@ -298,6 +304,28 @@ def search_cancel(pool: int, ticket: int) -> None:
 
 def search_sync(pool: int) -> None:
     _check(_lib.search_sync(ctypes.c_void_p(pool)), "search_sync")
+
+
+def search_run_stream(pool: int, queries: np.ndarray, arrival_s: np.ndarray, stride: int, depth: int = 0,
+                      nprobe_max: int = 0):
+    """Drive the pool through a stream (queries: QUERY_DTYPE array, arrival_s: seconds, not decreasing).
+    Returns (ids int64 [n, stride], dist fp32 [n, stride], n_out uint32 [n], done_s float64 [n], stats,
+    probes uint32 [n, nprobe_max] or None -- asked for by passing the pool's nprobe_max)."""
+    assert queries.dtype == QUERY_DTYPE and queries.flags["C_CONTIGUOUS"]
+    arrival_s = np.ascontiguousarray(arrival_s, dtype=np.float64)
+    n = queries.shape[0]
+    assert arrival_s.shape == (n,)
+    ids = np.full((n, stride), -1, dtype=np.int64)
+    dist = np.full((n, stride), np.nan, dtype=np.float32)
+    n_out = np.zeros(n, dtype=np.uint32)
+    done_s = np.zeros(n, dtype=np.float64)
+    stats = tri_stream_stats()
+    probes = np.zeros((n, nprobe_max), dtype=np.uint32) if nprobe_max else None
+    _check(_lib.search_run_stream(ctypes.c_void_p(pool), _np_ptr(queries), _np_ptr(arrival_s), n, depth, stride,
+                                  _np_ptr(n_out), _np_ptr(ids), _np_ptr(dist), _np_ptr(done_s), _np_ptr(probes),
+                                  ctypes.byref(stats)),
+           "search_run_stream")
+    return ids, dist, n_out, done_s, stats, probes
 
 
 # ------------------------------------------------------------------------------------------- holders

@@ -8,7 +8,9 @@
 #include <cstdarg>
 #include <cstdio>
 #include <cstring>
+#include <chrono>
 #include <deque>
+#include <thread>
 #include <mutex>
 #include <new>
 #include <string>
@@ -130,6 +132,9 @@ struct tri_pool {
     tri_kernel_times times{};
     // scratch vectors reused by search_step
     std::vector<uint32_t> order, newq;
+    // search_run_stream: tickets in the order their results arrived
+    bool log_done = false;
+    std::vector<uint32_t> done_log;
 };
 
 namespace {
@@ -254,6 +259,7 @@ int reap(tri_pool *P, bool block, uint32_t *finished)
             if (P->cfg.flags & TRI_FLAG_KEEP_PROBES)
                 memcpy(&P->res_probe[(size_t)ti * pmax], prb + i * (size_t)pmax, (size_t)t.nprobe * 4);
             t.state = T_DONE;
+            if (P->log_done) P->done_log.push_back(ti);
             ++fin;
         }
         if (R->profiled) {
@@ -1068,6 +1074,102 @@ extern "C" int search_sync(tri_pool *P)
     std::lock_guard<std::mutex> lk(P->mu);
     HIP_TRY(hipSetDevice(P->device));
     return reap(P, true, nullptr);
+}
+
+// ================================================================================== stream driver
+// The serving loop of Sec. 3.2 as one native call: arrivals are queued when their time has come, a
+// step is enqueued whenever there is work and fewer than `depth` steps are in flight, results are
+// collected as soon as their step completes.  No waiting to fill a batch: a step starts with whatever
+// is there (the paper's time-out flush with time-out zero).
+extern "C" int search_run_stream(tri_pool *P, const tri_query *q, const double *arrival_s, uint32_t n, uint32_t depth,
+                                 uint32_t stride, uint32_t *n_out, int64_t *ids, float *dist, double *done_s,
+                                 uint32_t *probes, tri_stream_stats *out)
+{
+    if (!P || !q || !arrival_s || !n_out || !ids || !dist || !done_s) return fail(TRI_EINVAL, "NULL argument");
+    if (n == 0) return fail(TRI_EINVAL, "empty stream");
+    if (probes && !(P->cfg.flags & TRI_FLAG_KEEP_PROBES))
+        return fail(TRI_EINVAL, "probe lists need a pool created with TRI_FLAG_KEEP_PROBES");
+    {
+        std::lock_guard<std::mutex> lk(P->mu);
+        if (P->free_tickets.size() != P->tickets.size()) return fail(TRI_EINVAL, "the pool has queries in flight");
+        for (uint32_t i = 0; i < n; ++i) {
+            int rc = validate_query(P, &q[i]);
+            if (rc) return rc;
+            if (q[i].k > stride) return fail(TRI_EINVAL, "query %u: k=%u exceeds the row stride %u", i, q[i].k, stride);
+            if (i && arrival_s[i] < arrival_s[i - 1]) return fail(TRI_EINVAL, "arrival times must not decrease");
+        }
+        P->log_done = true;
+        P->done_log.clear();
+    }
+    if (depth == 0) depth = 2;
+    if (depth > RING) depth = RING;
+    std::vector<uint32_t> q_of_ticket(P->tickets.size());
+    tri_stream_stats acc{};
+    using clk = std::chrono::steady_clock;
+    const clk::time_point t0 = clk::now();
+    auto elapsed = [&]() { return std::chrono::duration<double>(clk::now() - t0).count(); };
+    uint32_t next = 0, done = 0;
+    int rc = TRI_OK;
+    while (done < n && rc == TRI_OK) {
+        bool have_work = false;
+        uint32_t inflight = 0;
+        {
+            std::lock_guard<std::mutex> lk(P->mu);
+            const double now = elapsed();
+            while (next < n && arrival_s[next] <= now && !P->free_tickets.empty()) {
+                tri_ticket tk;
+                enqueue_locked(P, &q[next], &tk);
+                q_of_ticket[(uint32_t)(tk & 0xFFFFFFFFull)] = next;
+                ++next;
+            }
+            rc = hipSetDevice(P->device) == hipSuccess ? reap(P, false, nullptr) : fail(TRI_EHIP, "hipSetDevice failed");
+            if (rc) break;
+            if (!P->done_log.empty()) {
+                const double t = elapsed();
+                for (uint32_t ti : P->done_log) {
+                    const uint32_t qi = q_of_ticket[ti];
+                    const tri_ticket tk = ((uint64_t)P->tickets[ti].gen << 32) | ti;
+                    if (probes)
+                        memcpy(probes + (size_t)qi * P->cfg.nprobe_max, &P->res_probe[(size_t)ti * P->cfg.nprobe_max],
+                               (size_t)P->tickets[ti].nprobe * 4);
+                    rc = poll_locked(P, tk, &n_out[qi], ids + (size_t)qi * stride, dist + (size_t)qi * stride, stride);
+                    if (rc) break;
+                    done_s[qi] = t;
+                    ++done;
+                }
+                P->done_log.clear();
+                if (rc) break;
+            }
+            for (uint32_t i = 0; i < RING; ++i) inflight += P->ring[i].in_use;
+            const uint64_t waiting = P->pending[0].size() + P->pending[1].size();
+            have_work = P->n_running > 0 || waiting > 0;
+            if (waiting > acc.max_pending) acc.max_pending = waiting;
+        }
+        if (have_work && inflight < depth) {
+            tri_step_stats st;
+            rc = search_step(P, &st);
+            if (rc) break;
+            if (st.items) {
+                acc.steps += 1;
+                acc.items += st.items;
+                acc.capacity += st.capacity;
+                acc.running += st.running;
+            }
+        } else if (!have_work && inflight == 0 && next < n) {
+            const double wait = arrival_s[next] - elapsed();       // idle until the next arrival
+            if (wait > 200e-6) std::this_thread::sleep_for(std::chrono::duration<double>(wait - 100e-6));
+        } else {
+            std::this_thread::yield();                              // steps in flight: their events are polled above
+        }
+    }
+    acc.wall_s = elapsed();
+    {
+        std::lock_guard<std::mutex> lk(P->mu);
+        P->log_done = false;
+        P->done_log.clear();
+    }
+    if (out) *out = acc;
+    return rc;
 }
 
 extern "C" int tri_pool_kernel_times(tri_pool *P, tri_kernel_times *out, int reset)

@@ -314,6 +314,79 @@ def test_two_indexes_two_classes():
         assert later >= 22 - 7, f"only {later} of the 22 waiting low-class queries finished after the high-class one"
 
 
+@pytest.mark.parametrize("scale", ["scaled", "full"])
+@pytest.mark.timeout(900)
+def test_config3_stream_over_two_indexes(scale):
+    """Configuration 3: Poisson arrivals over a RAG index and a prompt-cache index in one pool, driven
+    by the library's native serving loop.  Every query is answered; a seeded sample (both kinds) equals
+    the oracle; the cache-hit flag (top-1 similarity >= 0.95) agrees with the oracle's top-1 outside the
+    tolerance band; latencies are consistent."""
+    import torch
+    tri = harness.lib()
+    if scale == "scaled":
+        rag_cfg = workloads.CONFIGS[2].scaled(n_base=60_000, n_components=256, nlist=256, n_queries=0)
+        cache_cfg = workloads.CACHE_INDEX.scaled(n_base=20_000, n_components=64, nlist=64, n_queries=0)
+        n, slots, rate, n_check = 3000, 256, 2.0e5, 120
+    else:
+        rag_cfg, cache_cfg = workloads.CONFIGS[2], workloads.CACHE_INDEX
+        n, slots, rate, n_check = 100_000, 4096, 4.0e5, 96
+    _say(f"config 3 {scale}: generate")
+    w = workloads.make_config3(n, "cuda", rag_cfg, cache_cfg)
+    torch.cuda.synchronize()
+    rag_base, cache_base = w["rag_base"].cpu().numpy(), w["cache_base"].cpu().numpy()
+    queries = np.ascontiguousarray(w["queries"].cpu().numpy())
+    arrival = workloads.poisson_arrivals(n, rate, 4003)
+    with harness.default_pool(tri, slots=slots, items_per_step=slots * 8, lists_per_query_step=8, kmax=128,
+                              nprobe_max=32, max_dim=768, max_nlist=rag_cfg.nlist,
+                              max_total_lists=rag_cfg.nlist + cache_cfg.nlist, max_outstanding=4 * slots,
+                              score_capacity=256 << 20) as pool:
+        _say(f"config 3 {scale}: build two indexes")
+        ir = pool.build_index(w["rag_base"], rag_cfg.dim, rag_cfg.nlist, tri.TRI_F16, tri.TRI_IP, rag_cfg.train_iters,
+                              centroids=rag_base[w["rag_rows"]].astype(np.float32))
+        ic = pool.build_index(w["cache_base"], cache_cfg.dim, cache_cfg.nlist, tri.TRI_F16, tri.TRI_IP,
+                              cache_cfg.train_iters, centroids=cache_base[w["cache_rows"]].astype(np.float32))
+        index_of = np.where(w["is_rag"], ir, ic).astype(np.uint64)
+        q = tri.make_queries(index_of, queries, w["k"], w["nprobe"], tri.TRI_IP, w["klass"])
+        _say(f"config 3 {scale}: stream of {n} queries at {rate:.0f}/s")
+        ids, dist, n_out, done_s, st, probes = tri.search_run_stream(pool.handle, q, arrival, 100, depth=2, nprobe_max=32)
+        lat = done_s - arrival
+        _say(f"config 3 {scale}: {n / st.wall_s:.0f} q/s over {st.steps} steps, padding "
+             f"{1 - st.items / max(st.capacity, 1):.3f}, latency p50 {np.percentile(lat, 50) * 1e3:.2f} ms "
+             f"p99 {np.percentile(lat, 99) * 1e3:.2f} ms, longest queue {st.max_pending}")
+        # every query answered, in time order
+        assert np.all(n_out == w["k"]) and np.all(lat > 0) and done_s.max() <= st.wall_s
+        assert st.items <= st.capacity and st.items == int(w["nprobe"].sum())
+        k = w["k"]
+        assert all(ids[i, :k[i]].min() >= 0 for i in range(0, n, 37))
+        # the high class (cache lookups: one step each) does not wait behind the low class
+        hi, lo = lat[~w["is_rag"]], lat[w["is_rag"]]
+        _say(f"config 3 {scale}: mean latency cache {hi.mean() * 1e3:.2f} ms, RAG {lo.mean() * 1e3:.2f} ms")
+        assert np.median(hi) <= np.median(lo)
+        # parity on a sample of each kind
+        rng = np.random.default_rng(33)
+        for name, sel, idx, base in (("RAG", np.flatnonzero(w["is_rag"]), ir, rag_base),
+                                     ("cache", np.flatnonzero(~w["is_rag"]), ic, cache_base)):
+            sample = np.sort(rng.choice(sel, n_check // 2, replace=False))
+            oidx = harness.oracle_index(tri, idx, base)
+            pl = [probes[i, :w["nprobe"][i]] for i in range(n)]
+            rep = harness.compare_with_oracle(oidx, base, queries, w["k"], w["nprobe"], 1, ids, dist, n_out, pl,
+                                              sample=sample)
+            _say(f"config 3 {scale}: {name} parity {rep}")
+            if name == "cache":
+                # hit flag against the oracle's top-1 score
+                flips = 0
+                for i in sample:
+                    top = float(oracle.search(oidx, queries[i], 1, int(w["nprobe"][i]), 1)[2][0])
+                    if abs(top - 0.95) > 2e-3 * 0.95 + checker.ABS_EPS:
+                        assert (dist[i, 0] >= 0.95) == (top >= 0.95)
+                    else:
+                        flips += 1
+                hits = dist[~w["is_rag"], 0] >= 0.95
+                dup = w["near_dup"][~w["is_rag"]]
+                _say(f"config 3 {scale}: hit rate {hits.mean():.3f}, near-duplicates {dup.mean():.3f}, in band {flips}")
+                assert hits[dup].mean() > 0.98 and hits[~dup].mean() < 0.02
+
+
 @pytest.mark.timeout(900)
 def test_config4_full_size_in_the_benchmark_configuration():
     """Configuration 4 at full size (10M x 768 fp16, nlist 16384, 4096 queries, nprobe 64, k 100) in

@@ -208,3 +208,44 @@ def make_config_f16(cfg: Config, device: str = "cpu"):
     queries, _ = unit_mixture_f16(max(cfg.n_queries, 1), cfg.dim, cfg.n_components, cfg.seed_data,
                                   cfg.seed_queries, device=device)
     return base, queries[:cfg.n_queries], kmeans_seed_rows(cfg.n_base, cfg.nlist, cfg.seed_kmeans)
+
+
+def make_config3(n_queries: int, device: str = "cpu", rag_cfg: Optional[Config] = None,
+                 cache_cfg: Optional[Config] = None):
+    """Configuration 3: a stream over two indexes (torch tensors on ``device``).
+
+    RAG index = configuration 2's base; prompt-cache index = CACHE_INDEX.  Query i is a RAG query
+    (fresh draw from the RAG mixture) or a cache lookup: a near-duplicate of a stored cache vector
+    (cosine about 0.99: an expected hit) or a fresh draw from the cache mixture (an expected miss).
+    Returns a dict: rag_base, cache_base, rag_rows, cache_rows (k-means seed rows), queries fp16 [n, d]
+    in arrival order, is_rag, k, nprobe, klass, near_dup, dup_of (cache row a near-duplicate copies, else -1).
+    """
+    import torch
+    rag_cfg = rag_cfg or CONFIGS[2]
+    cache_cfg = cache_cfg or CACHE_INDEX
+    rag_base, _ = unit_mixture_f16(rag_cfg.n_base, rag_cfg.dim, rag_cfg.n_components, rag_cfg.seed_data,
+                                   rag_cfg.seed_data + 500, device=device)
+    cache_base, _ = unit_mixture_f16(cache_cfg.n_base, cache_cfg.dim, cache_cfg.n_components, cache_cfg.seed_data,
+                                     cache_cfg.seed_data + 500, device=device)
+    is_rag, k, nprobe, klass, near_dup = stream_mix(n_queries, 4003)
+    n_rag, n_dup = int(is_rag.sum()), int(near_dup.sum())
+    n_fresh = n_queries - n_rag - n_dup
+    queries = torch.empty((n_queries, rag_cfg.dim), dtype=torch.float16, device=device)
+    if n_rag:
+        qr, _ = unit_mixture_f16(n_rag, rag_cfg.dim, rag_cfg.n_components, rag_cfg.seed_data, 2003, device=device)
+        queries[torch.from_numpy(np.flatnonzero(is_rag)).to(device)] = qr
+    fresh = (~is_rag) & (~near_dup)
+    if n_fresh:
+        qf, _ = unit_mixture_f16(n_fresh, cache_cfg.dim, cache_cfg.n_components, cache_cfg.seed_data, 2004,
+                                 device=device)
+        queries[torch.from_numpy(np.flatnonzero(fresh)).to(device)] = qf
+    dup_of = np.full(n_queries, -1, dtype=np.int64)
+    if n_dup:
+        src = np.random.default_rng(4004).integers(0, cache_cfg.n_base, size=n_dup)
+        dup_of[near_dup] = src
+        qd = perturbed_copies_f16(cache_base[torch.from_numpy(src).to(device)], 2005)
+        queries[torch.from_numpy(np.flatnonzero(near_dup)).to(device)] = qd
+    return dict(rag_base=rag_base, cache_base=cache_base,
+                rag_rows=kmeans_seed_rows(rag_cfg.n_base, rag_cfg.nlist, rag_cfg.seed_kmeans),
+                cache_rows=kmeans_seed_rows(cache_cfg.n_base, cache_cfg.nlist, cache_cfg.seed_kmeans),
+                queries=queries, is_rag=is_rag, k=k, nprobe=nprobe, klass=klass, near_dup=near_dup, dup_of=dup_of)
