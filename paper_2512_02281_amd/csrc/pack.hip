@@ -113,16 +113,13 @@ __global__ void pack_emit_kernel(const TriPlanEntry *__restrict__ plan, uint32_t
 //     shortest), of: items per list (-> list_start), tiles per list (-> tile_base), padded scores
 //     per list (-> score_base).  Also the step totals and the reset of the work-queue heads.
 __global__ __launch_bounds__(1024) void pack_scan_kernel(const uint32_t *__restrict__ hist, uint32_t n_order,
-                                                         const uint32_t *__restrict__ glist_order,
-                                                         const uint32_t *__restrict__ glist_len,
-                                                         const uint32_t *__restrict__ glist_index,
-                                                         const TriIndexDev *__restrict__ indexes,
+                                                         const uint4 *__restrict__ order,
                                                          uint32_t *__restrict__ list_start,
                                                          uint32_t *__restrict__ tile_base,
                                                          uint32_t *__restrict__ stile_base,
                                                          uint64_t *__restrict__ score_base,
                                                          TriStepDev *__restrict__ step_dev,
-                                                         uint32_t *__restrict__ tile_counter, uint32_t chunk_vecs)
+                                                         uint32_t *__restrict__ tile_counter)
 {
     __shared__ uint32_t s_items[1024], s_tiles[1024], s_lists[1024], s_stiles[1024];
     __shared__ uint64_t s_scores[1024], s_tbytes[1024], s_ubytes[1024];
@@ -131,20 +128,29 @@ __global__ __launch_bounds__(1024) void pack_scan_kernel(const uint32_t *__restr
     const uint32_t i0 = min(t * per, n_order), i1 = min(i0 + per, n_order);
     uint32_t items = 0, tiles = 0, lists = 0, stiles = 0;
     uint64_t sc = 0, tb = 0, ub = 0;
-    for (uint32_t i = i0; i < i1; ++i) {
-        const uint32_t g = glist_order[i];
-        const uint32_t c = hist[g];
-        if (c) {
-            const uint32_t len = glist_len[g];
-            const uint32_t nt = (c + TRI_QT - 1) / TRI_QT;
-            const uint64_t bytes = (uint64_t)len * indexes[glist_index[g]].row_bytes;
-            items += c;
-            tiles += nt * ((len + chunk_vecs - 1) / chunk_vecs);
-            stiles += len ? nt : 0;
-            lists += 1;
-            sc += (uint64_t)c * 2u * ((len + TRI_VB - 1) / TRI_VB * TRI_VB);
-            tb += bytes * nt;
-            ub += bytes;
+    // (entries {list, length, row bytes, chunks} are static; only the item counts are gathered, several at once)
+    for (uint32_t ib = i0; ib < i1; ib += 8) {
+        uint4 o[8];
+        uint32_t cnt[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) o[u] = ib + u < i1 ? order[ib + u] : make_uint4(0u, 0u, 0u, 0u);
+#pragma unroll
+        for (int u = 0; u < 8; ++u) cnt[u] = ib + u < i1 ? hist[o[u].x] : 0u;
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            const uint32_t c = cnt[u];
+            if (c) {
+                const uint32_t len = o[u].y;
+                const uint32_t nt = (c + TRI_QT - 1) / TRI_QT;
+                const uint64_t bytes = (uint64_t)len * o[u].z;
+                items += c;
+                tiles += nt * o[u].w;
+                stiles += len ? nt : 0;
+                lists += 1;
+                sc += (uint64_t)c * 2u * ((len + TRI_VB - 1) / TRI_VB * TRI_VB);
+                tb += bytes * nt;
+                ub += bytes;
+            }
         }
     }
     s_items[t] = items; s_tiles[t] = tiles; s_lists[t] = lists; s_stiles[t] = stiles;
@@ -165,19 +171,27 @@ __global__ __launch_bounds__(1024) void pack_scan_kernel(const uint32_t *__restr
     }
     uint32_t it = s_items[t] - items, ti = s_tiles[t] - tiles, sti = s_stiles[t] - stiles;
     uint64_t so = s_scores[t] - sc;
-    for (uint32_t i = i0; i < i1; ++i) {
-        const uint32_t g = glist_order[i];
-        const uint32_t c = hist[g];
-        list_start[g] = it;
-        tile_base[g] = ti;
-        stile_base[g] = sti;
-        score_base[g] = so;
-        if (c) {
-            const uint32_t len = glist_len[g];
-            it += c;
-            ti += (c + TRI_QT - 1) / TRI_QT * ((len + chunk_vecs - 1) / chunk_vecs);
-            sti += len ? (c + TRI_QT - 1) / TRI_QT : 0;
-            so += (uint64_t)c * 2u * ((len + TRI_VB - 1) / TRI_VB * TRI_VB);
+    for (uint32_t ib = i0; ib < i1; ib += 8) {
+        uint4 o[8];
+        uint32_t cnt[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) o[u] = ib + u < i1 ? order[ib + u] : make_uint4(0u, 0u, 0u, 0u);
+#pragma unroll
+        for (int u = 0; u < 8; ++u) cnt[u] = ib + u < i1 ? hist[o[u].x] : 0u;
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            if (ib + u >= i1) break;
+            const uint32_t g = o[u].x, c = cnt[u], len = o[u].y;
+            list_start[g] = it;
+            tile_base[g] = ti;
+            stile_base[g] = sti;
+            score_base[g] = so;
+            if (c) {
+                it += c;
+                ti += (c + TRI_QT - 1) / TRI_QT * o[u].w;
+                sti += len ? (c + TRI_QT - 1) / TRI_QT : 0;
+                so += (uint64_t)c * 2u * ((len + TRI_VB - 1) / TRI_VB * TRI_VB);
+            }
         }
     }
     if (t == 1023) {
@@ -270,9 +284,8 @@ hipError_t tri_launch_pack(const TriLaunchCtx &c, const TriDevWs &ws, const TriP
     hipLaunchKernelGGL(pack_emit_kernel, dim3((n_items + 255) / 256), dim3(256), 0, c.stream, plan_dev, n_plan,
                        n_items, ws.slot_meta, ws.indexes, ws.probe, c.nprobe_max, ws.item_glist, ws.item_slot,
                        ws.item_rank, ws.hist);
-    hipLaunchKernelGGL(pack_scan_kernel, dim3(1), dim3(1024), 0, c.stream, ws.hist, n_order, ws.glist_order, ws.glist_len,
-                       ws.glist_index, ws.indexes, ws.list_start, ws.tile_base, ws.stile_base, ws.score_base,
-                       ws.step_dev, ws.tile_counter, chunk_vecs);
+    hipLaunchKernelGGL(pack_scan_kernel, dim3(1), dim3(1024), 0, c.stream, ws.hist, n_order, ws.glist_order, ws.list_start,
+                       ws.tile_base, ws.stile_base, ws.score_base, ws.step_dev, ws.tile_counter);
     hipLaunchKernelGGL(pack_scatter_kernel, dim3((n_items + 255) / 256), dim3(256), 0, c.stream, n_items,
                        ws.item_glist, ws.item_slot, ws.item_rank, ws.list_start, ws.score_base, ws.glist_len,
                        ws.sorted_slot, ws.item_score_off, ws.item_sorted_pos);

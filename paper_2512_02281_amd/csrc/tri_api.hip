@@ -7,6 +7,7 @@
 #include <algorithm>
 #include <cstdarg>
 #include <cstdio>
+#include <cstdlib>
 #include <cstring>
 #include <chrono>
 #include <deque>
@@ -163,7 +164,7 @@ size_t carve(const tri_pool_cfg &c, uint32_t max_row_bytes, uint32_t coarse_rows
     CARVE(glist_len, uint32_t *, G * 4)
     CARVE(glist_voff, uint32_t *, G * 4)
     CARVE(glist_index, uint32_t *, G * 4)
-    CARVE(glist_order, uint32_t *, G * 4)
+    CARVE(glist_order, uint4 *, G * 16)
     CARVE(upload, uint8_t *, upload_bytes)
     CARVE(coarse_scores, float *, (size_t)coarse_rows * coarse_ldc * 4)
     CARVE(item_glist, uint32_t *, W * 4)
@@ -298,15 +299,28 @@ int upload_scan_order(tri_pool *P)
     std::stable_sort(v.begin(), v.end(), [](const std::pair<uint64_t, uint32_t> &a, const std::pair<uint64_t, uint32_t> &b) {
         return a.first > b.first;
     });
-    std::vector<uint32_t> order(v.size());
-    for (size_t i = 0; i < v.size(); ++i) order[i] = v[i].second;
-    if (!order.empty())
-        HIP_TRY(hipMemcpy(P->ws.glist_order, order.data(), order.size() * 4, hipMemcpyHostToDevice));
-    P->n_order = (uint32_t)order.size();
     uint32_t longest = 0;
     for (tri_index *ix : P->indexes)
         if (ix) longest = std::max(longest, ix->max_list_len);
     P->chunk_vecs = std::max(1024u, round_up((longest + TRI_TILES_PER_ITEM - 1) / TRI_TILES_PER_ITEM, TRI_VB));
+    // per entry everything the per-step prefix sums need, so that they read this array front to back
+    std::vector<uint4> order(v.size());
+    uint32_t extent = 0;
+    for (tri_index *ix : P->indexes)
+        if (ix) extent = std::max(extent, ix->list_base + ix->p.nlist);
+    std::vector<const tri_index *> owner(extent, nullptr);
+    for (tri_index *ix : P->indexes)
+        if (ix)
+            for (uint32_t l = 0; l < ix->p.nlist; ++l) owner[ix->list_base + l] = ix;
+    for (size_t i = 0; i < v.size(); ++i) {
+        const uint32_t g = v[i].second;
+        const tri_index *ix = owner[g];
+        const uint32_t len = ix->list_len[g - ix->list_base];
+        order[i] = make_uint4(g, len, ix->row_bytes, (len + P->chunk_vecs - 1) / P->chunk_vecs);
+    }
+    if (!order.empty())
+        HIP_TRY(hipMemcpy(P->ws.glist_order, order.data(), order.size() * sizeof(uint4), hipMemcpyHostToDevice));
+    P->n_order = (uint32_t)order.size();
     return TRI_OK;
 }
 
@@ -934,6 +948,8 @@ extern "C" int search_step(tri_pool *P, tri_step_stats *st)
     if (n_items) HIP_TRY(tri_launch_scan(P->ctx, P->ws, P->attached_row_bytes, P->scan_class_mask, false));
     if (prof) HIP_TRY(hipEventRecord(R.ev[5], s));
     HIP_TRY(tri_launch_merge(P->ctx, P->ws, plan_d, n_plan, (cfg.flags & TRI_FLAG_KEEP_PROBES) != 0, P->chunk_vecs));
+    // (the result copy stays on the pool's stream: on a second stream it ran beside the next step's
+    // scan and slowed that by far more than the transfer takes)
     if (n_retire) {
         HIP_TRY(hipMemcpyAsync(R.down_host, P->ws.res_block, (size_t)n_retire * (1 + 2 * (size_t)cfg.kmax) * 4,
                                hipMemcpyDeviceToHost, s));

@@ -117,7 +117,8 @@ struct TriDevWs {
     uint32_t *glist_len;      // [max_total_lists]
     uint32_t *glist_voff;     // [max_total_lists] first stored position inside its index
     uint32_t *glist_index;    // [max_total_lists]
-    uint32_t *glist_order;    // [max_total_lists] attached lists by descending byte length (scan order)
+    uint4 *glist_order;       // [max_total_lists] attached lists by descending byte length (scan order):
+                              //   {pool-wide list number, length, row bytes, chunks}
     // per-step upload block (device copy)
     uint8_t *upload;          // upload_bytes
     // coarse ranking
