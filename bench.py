@@ -26,6 +26,10 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0   # MI355X published HBM3E bandwidth
+# HBM bytes one launch of the list-scan kernel moves at configuration 4, measured with rocprofv3 --pmc
+# FETCH_SIZE / WRITE_SIZE (each scaled by the same counter's reading for a 1 GiB device copy); the runs
+# are summarised in profiles/scan_kernel_config4.txt.  Not measurable from inside this script.
+MEASURED_TRAFFIC_BYTES = {4: 16.001e9}
 
 
 def log(msg):
@@ -41,6 +45,9 @@ def main():
     ap.add_argument("--stream-queries", type=int, default=100_000, help="config3: queries in the stream")
     ap.add_argument("--cpu-sample", type=int, default=-1, help="queries timed on the CPU oracle (0 = skip)")
     ap.add_argument("--recall-sample", type=int, default=64)
+    ap.add_argument("--host-queries", action="store_true",
+                    help="submit the query vectors from host memory (adds their PCIe transfer to every step; "
+                         "a side measurement, never the headline value)")
     ap.add_argument("--copy-calibration-mib", type=int, default=0,
                     help="run one plain device copy of this many MiB before timing (a kernel of known traffic, "
                          "to scale profiler byte counters)")
@@ -101,8 +108,16 @@ def main():
     es = 2 if dtype == tri.TRI_F16 else 4
     qptr, pitch = queries_t.data_ptr(), cfg.dim * es
 
+    host_q = None
+    if args.host_queries:
+        queries_host = np.ascontiguousarray(queries_t.cpu().numpy())
+        host_q = tri.make_queries(index, queries_host, k, nprobe, metric_arr)
+
     def one_batch():
-        tickets, rc = tri.search_submit_batch_dev(pool.handle, index, qptr, pitch, Q, k, nprobe, metric_arr)
+        if host_q is not None:
+            tickets, rc = tri.search_submit_batch(pool.handle, host_q)
+        else:
+            tickets, rc = tri.search_submit_batch_dev(pool.handle, index, qptr, pitch, Q, k, nprobe, metric_arr)
         assert rc == tri.TRI_OK and tickets.shape[0] == Q
         launches = 0
         while True:
@@ -211,10 +226,11 @@ def main():
                                f"k {kmax if number != 2 else 'U{1,10,100}'}",
                    "queries_per_step": Q, "items_per_step": items, "launches_per_step": launches_per_batch,
                    "recall_at_k": None if recall is None else round(recall, 4),
-                   "longest_list": info["max_list_len"], "query_vectors": "device-resident"},
+                   "longest_list": info["max_list_len"],
+                   "query_vectors": "host memory (PCIe-inclusive side measurement)" if args.host_queries else "device-resident"},
         "roofline": {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": None,
-                     "kernel": "scan_kernel", "avg_launch_ms": round(scan_ms, 4),
+                     "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": MEASURED_TRAFFIC_BYTES.get(number),
+                     "kernel": "scan_wave_kernel (main launch)", "avg_launch_ms": round(scan_ms, 4),
                      "algorithmic_bytes_per_launch": int(unique_b), "tile_bytes_per_launch": int(tile_b),
                      "items_per_launch": int(kt.scan_items / max(kt.scan_launches, 1)), "row_bytes": row_bytes},
         "stages_ms_per_step": {"admit": round(kt.admit_ms / kt.steps, 4), "coarse": round(kt.coarse_ms / kt.steps, 4),
