@@ -59,7 +59,7 @@ enum { TRI_FLAG_PROFILE = 1u,             /* bracket every kernel of a step with
 #define TRI_MAX_ROW_BYTES 4096u   /* padded vector row: dim <= 2048 (fp16), 1024 (fp32) */
 
 typedef struct {
-    uint32_t slots;                /* S: running requests held at once (Sec. 3.3 "available slots")        */
+    uint32_t slots;                /* S: running requests held at once (the slot count of Sec. 3.3)        */
     uint32_t items_per_step;       /* W: capacity of the cross-request task array, in (query, list) items    */
     uint32_t lists_per_query_step; /* p: lists a request may scan per step; 0 = all that remain             */
     uint32_t kmax;                 /* largest k accepted                                                   */
@@ -208,8 +208,8 @@ int search_cancel(tri_pool *pool, tri_ticket t);
 /* Block until all enqueued steps have completed and their results are pollable. */
 int search_sync(tri_pool *pool);
 
-/* The serving loop of Sec. 3.2 ("new arrivals are admitted and contribute tasks to the next batch ...
- * completed requests exit immediately") as one native call, for measuring a stream: query i is
+/* The serving loop of Sec. 3.2 (arrivals join at the next batch boundary, finished requests leave
+ * at once) as one native call, for measuring a stream: query i is
  * queued when arrival_s[i] seconds have passed since the call began (its vector is copied then), a
  * step is enqueued whenever there is work and fewer than `depth` steps are in flight (0 = 2; at most
  * 4) -- never waiting for a batch to fill --, and every result is stored as soon as its step has

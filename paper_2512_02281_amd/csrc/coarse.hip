@@ -1,5 +1,5 @@
 // Coarse assignment: scores of query rows against an index's centroids as a dense contraction
-// on the matrix cores (IVF replacement for "select the parents to expand" in the paper's
+// on the matrix cores (the IVF counterpart of choosing which parents to expand in the paper's
 // Sec. 3.2 step loop; also the assignment pass of index construction).
 //
 //   C[m][n] = L2:  |b_n|^2 - 2 a_m.b_n      (the per-query constant |a_m|^2 does not change a ranking)

@@ -1,4 +1,4 @@
-// List scan: the "global distance stage" of the paper's Sec. 3.2 -- fixed-shape kernels that
+// List scan: the batched distance stage of the paper's Sec. 3.2 -- fixed-shape kernels that
 // evaluate every accumulated distance task of the step.  A task here is (query slot, inverted
 // list); tasks on the same list were packed next to each other, so a tile = (list chunk, up to
 // TRI_QT of its queries) streams the chunk's vectors from HBM ONCE and scores them against all of

@@ -1,5 +1,5 @@
-// Per-query top-k (the paper's Sec. 3.2 step "scatter (id, dist) back to the owning request and
-// merge into its topM"; here the request's candidates of one step are the (score, position) pairs the
+// Per-query top-k (Sec. 3.2 of the paper: the step that returns each distance to the request it
+// belongs to and merges it into that request's candidate list; here the request's candidates of one step are the (score, position) pairs the
 // scan kept for its work items plus its running top-k).
 //
 // Order: ascending 64-bit composite (key << 32 | id), key = order-preserving image of the fp32
