@@ -314,6 +314,73 @@ def test_two_indexes_two_classes():
         assert later >= 22 - 7, f"only {later} of the 22 waiting low-class queries finished after the high-class one"
 
 
+@pytest.mark.parametrize("dtype,dim", [("f32", 256), ("f32", 384), ("f32", 512), ("f32", 160),
+                                       ("f16", 256), ("f16", 512), ("f16", 1024), ("f16", 320)])
+def test_every_row_length_class_and_long_lists(dtype, dim):
+    """One case per scan-kernel variant not met by the five configurations (rows of 512 / 1024 / 1536 /
+    2048 bytes and other lengths, both storage types), with lists long enough to be scanned in several
+    chunks, k from 1 to 1000 (no threshold below k sample scores, more candidates than fit in LDS) and
+    both metrics."""
+    import torch
+    tri = harness.lib()
+    rng = np.random.default_rng(dim + (7 if dtype == "f16" else 0))
+    n, nlist, nq = 30_000, 24, 64
+    centres = rng.standard_normal((nlist, dim)).astype(np.float32)
+    base = (centres[rng.integers(0, nlist, size=n)] + 0.7 * rng.standard_normal((n, dim))).astype(np.float32)
+    queries = (centres[rng.integers(0, nlist, size=nq)] + 0.7 * rng.standard_normal((nq, dim))).astype(np.float32)
+    if dtype == "f16":
+        scale = 1.0 / np.sqrt(dim)                      # keep squared norms far from the fp16 range limit
+        base, queries = (base * scale).astype(np.float16), (queries * scale).astype(np.float16)
+        tdt = tri.TRI_F16
+    else:
+        tdt = tri.TRI_F32
+    k = rng.choice(np.array([1, 10, 300, 1000], dtype=np.uint32), size=nq)
+    nprobe = rng.integers(1, nlist + 1, size=nq).astype(np.uint32)
+    metric = (np.arange(nq) % 2).astype(np.uint32)
+    with harness.default_pool(tri, slots=64, items_per_step=64 * nlist, kmax=1024, nprobe_max=nlist, max_dim=dim,
+                              max_nlist=nlist, max_total_lists=nlist, score_capacity=64 << 20) as pool:
+        idx = pool.build_index(base, dim, nlist, tdt, tri.TRI_L2, 4, centroids=centres)
+        info = tri.ivf_info(idx)
+        _say(f"{dtype} d={dim}: longest list {info['max_list_len']}")
+        assert info["max_list_len"] > 1100                # several chunks per list
+        oidx = harness.oracle_index(tri, idx, base)
+        q = tri.make_queries(idx, queries, k, nprobe, metric)
+        ids, dist, n_out, probes, stats = harness.run_all(tri, pool, q)
+        rep = harness.compare_with_oracle(oidx, base, queries, k, nprobe, metric, ids, dist, n_out, probes)
+        _say(f"{dtype} d={dim}: parity {rep}")
+        # the same through three lists per step: thresholds then come from the running top-k as well
+        with harness.default_pool(tri, slots=16, items_per_step=48, lists_per_query_step=3, kmax=1024, nprobe_max=nlist,
+                                  max_dim=dim, max_nlist=nlist, max_total_lists=nlist, score_capacity=64 << 20) as pool2:
+            idx2 = pool2.build_index(base, dim, nlist, tdt, tri.TRI_L2, 4, centroids=centres)
+            q2 = tri.make_queries(idx2, queries, k, nprobe, metric)
+            ids2, dist2, n2, probes2, stats2 = harness.run_all(tri, pool2, q2)
+            assert np.array_equal(ids, ids2) and np.array_equal(n_out, n2)
+            assert np.array_equal(dist.view(np.uint32), dist2.view(np.uint32))
+
+
+def test_more_probed_lists_than_cached_segments():
+    """nprobe far beyond what the merge kernel caches of candidate segments (200 lists x 4 chunk
+    segments in one step), small lists, and a k that keeps nearly everything."""
+    tri = harness.lib()
+    rng = np.random.default_rng(21)
+    n, dim, nlist, nq = 20_000, 64, 200, 48
+    centres = rng.standard_normal((nlist, dim)).astype(np.float32) * 2
+    base = (centres[rng.integers(0, nlist, size=n)] + rng.standard_normal((n, dim))).astype(np.float32)
+    queries = (centres[rng.integers(0, nlist, size=nq)] + rng.standard_normal((nq, dim))).astype(np.float32)
+    k = rng.choice(np.array([5, 100, 900], dtype=np.uint32), size=nq)
+    nprobe = rng.choice(np.array([150, 200], dtype=np.uint32), size=nq)
+    metric = (np.arange(nq) % 2).astype(np.uint32)
+    with harness.default_pool(tri, slots=48, items_per_step=48 * 200, kmax=1024, nprobe_max=200, max_dim=dim,
+                              max_nlist=nlist, max_total_lists=nlist, score_capacity=64 << 20) as pool:
+        idx = pool.build_index(base, dim, nlist, tri.TRI_F32, tri.TRI_L2, 3, centroids=centres)
+        oidx = harness.oracle_index(tri, idx, base)
+        q = tri.make_queries(idx, queries, k, nprobe, metric)
+        ids, dist, n_out, probes, stats = harness.run_all(tri, pool, q)
+        assert len(stats) <= 3                            # everything in one scanning step
+        rep = harness.compare_with_oracle(oidx, base, queries, k, nprobe, metric, ids, dist, n_out, probes)
+        _say(f"many segments: parity {rep}")
+
+
 @pytest.mark.parametrize("scale", ["scaled", "full"])
 @pytest.mark.timeout(900)
 def test_config3_stream_over_two_indexes(scale):
