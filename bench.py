@@ -257,7 +257,7 @@ def stream_bench(args, tri, workloads, torch):
     queries = np.ascontiguousarray(w["queries"].cpu().numpy())
     pool = tri.Pool(slots=slots, items_per_step=slots * p, lists_per_query_step=p, kmax=128, nprobe_max=32,
                     max_indexes=2, max_total_lists=rag_cfg.nlist + cache_cfg.nlist, max_nlist=rag_cfg.nlist,
-                    max_dim=768, max_outstanding=4 * slots, coarse_rows=0, flags=tri.TRI_FLAG_PROFILE,
+                    max_dim=768, max_outstanding=n, coarse_rows=0, flags=tri.TRI_FLAG_PROFILE,
                     score_capacity=256 << 20)
     log("building the two indexes (untimed)")
     init_r = w["rag_base"][torch.from_numpy(w["rag_rows"]).cuda()].float().cpu().numpy()
@@ -268,9 +268,11 @@ def stream_bench(args, tri, workloads, torch):
     q = tri.make_queries(index_of, queries, w["k"], w["nprobe"], tri.TRI_IP, w["klass"])
     is_rag = w["is_rag"]
 
-    def run(arrival, label):
+    def run(arrival, label, qq=None, **policy):
+        qq = q if qq is None else qq
+        tri.search_set_policy(pool.handle, **policy)
         tri.tri_pool_kernel_times(pool.handle, reset=True)
-        ids, dist, n_out, done_s, st, _ = tri.search_run_stream(pool.handle, q, arrival, 100, depth=2)
+        ids, dist, n_out, done_s, st, _ = tri.search_run_stream(pool.handle, qq, arrival, 100, depth=2)
         lat = (done_s - arrival) * 1e3
         kt = tri.tri_pool_kernel_times(pool.handle)
         pct = lambda a: [round(float(np.percentile(a, x)), 3) for x in (50, 99)]
@@ -294,6 +296,20 @@ def stream_bench(args, tri, workloads, torch):
     for frac in (0.5, 0.8):
         runs.append(run(workloads.poisson_arrivals(n, frac * t_sat, 4003), f"Poisson arrivals at {frac} x saturation")[0])
     runs.append(run(workloads.poisson_arrivals(n, 1.0e5, 4003), "Poisson arrivals at 100,000 / s")[0])
+    # the step-boundary policy (Sec. 3.3) where slots are scarce -- a burst, everything offered at once:
+    # one queue, two classes with the cache lookups first, a reserved share, and least-slack order with
+    # a budget on the cache lookups
+    burst = np.zeros(n)
+    q_one = q.copy()
+    q_one["klass"] = tri.TRI_CLASS_LOW
+    q_ddl = q.copy()
+    q_ddl["deadline_ns"] = np.where(is_rag, 0, 20_000_000)
+    runs.append(run(burst, "burst, one class (first-in first-out only)", qq=q_one)[0])
+    runs.append(run(burst, "burst, two classes, high class first (share 1)")[0])
+    runs.append(run(burst, "burst, two classes, reserved share 0.3", high_share=0.3)[0])
+    runs.append(run(burst, "burst, reserved share 0.3, least slack first, 20 ms budget on cache lookups",
+                    qq=q_ddl, high_share=0.3, order_high=tri.TRI_ORDER_SLACK)[0])
+    tri.search_set_policy(pool.handle)
 
     cpu = None
     n_cpu = args.cpu_sample if args.cpu_sample >= 0 else 512

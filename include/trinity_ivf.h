@@ -144,7 +144,9 @@ typedef struct {
     uint32_t nprobe;        /* 1..min(nprobe_max, nlist) inverted lists to scan                     */
     uint32_t metric;        /* TRI_L2 / TRI_IP: used for the coarse ranking AND the list scan       */
     uint32_t klass;         /* TRI_CLASS_HIGH / TRI_CLASS_LOW                                       */
-    uint64_t deadline_ns;   /* carried, reported back; not yet used for ordering                    */
+    uint64_t deadline_ns;   /* latency budget in ns from the moment of submission (the L_pre,max of
+                               Sec. 3.3: deadline = arrival + budget); 0 = none.  Used by
+                               TRI_ORDER_SLACK, see tri_policy                                      */
     uint64_t user_tag;      /* carried, not interpreted                                             */
 } tri_query;
 
@@ -207,6 +209,43 @@ int search_cancel(tri_pool *pool, tri_ticket t);
 
 /* Block until all enqueued steps have completed and their results are pollable. */
 int search_sync(tri_pool *pool);
+
+/* ---------------------------------------------------------------------------------------
+ * Scheduling policy at step boundaries (Sec. 3.3: two queues, a reserved share for the
+ * latency-critical one, deadline-and-slack order inside it, short flush time-outs).  The high
+ * class plays the part of the paper's prefill queue, the low class that of its decode queue.
+ * May be changed between steps at any time (the paper's control loop does so every few hundred
+ * milliseconds; that loop itself is not part of this library).
+ * ------------------------------------------------------------------------------------- */
+enum { TRI_ORDER_FIFO = 0, TRI_ORDER_SLACK = 1 };
+typedef struct {
+    float high_share;       /* r in [0,1]: of the N slots free at a boundary, ceil(r*N) are offered to
+                               the high class first and the rest to the low class first; what one
+                               class cannot use goes to the other.  1 (default): high class first   */
+    uint32_t order_high;    /* TRI_ORDER_FIFO (default): high-class queue in arrival order.
+                               TRI_ORDER_SLACK: least slack first, slack = deadline - (now + E * T),
+                               E = steps the query still needs = ceil(nprobe / p), T = measured mean
+                               duration of a step; queries without a deadline come last, in arrival
+                               order.  The low class is always first-in first-out                  */
+    double flush_timeout_s;      /* search_run_stream only: an idle pool (nothing running) starts its next
+                                    step when its slot table can be filled, or when the oldest waiting
+                                    query has waited this long (0, default: at once) ...              */
+    double flush_timeout_high_s; /* ... or when the oldest waiting high-class query has waited this long */
+} tri_policy;
+int search_set_policy(tri_pool *pool, const tri_policy *policy /*[host]*/);
+/* The policy in force and T, the mean step duration the slack order uses (seconds; 0 before the
+ * first step has completed).  Either output may be NULL. */
+int search_get_policy(tri_pool *pool, tri_policy *policy /*[host] out*/, double *mean_step_s /*[host] out*/);
+
+/* The two rules above as pure functions (no GPU, no pool), the way search_step applies them.
+ * tri_policy_split: how many queries of each class are admitted into free_slots slots.
+ * tri_policy_slack_order: order[0..m) = the m indices of least slack, by ascending slack (ties and
+ * queries without a deadline, deadline_ns[i] = INT64_MAX, by index); order[m..n) = the other indices,
+ * ascending (they keep their arrival order).  Deadlines and now on one clock, in ns. */
+int tri_policy_split(uint32_t free_slots, uint32_t n_high, uint32_t n_low, float high_share,
+                     uint32_t *take_high /*[host] out*/, uint32_t *take_low /*[host] out*/);
+int tri_policy_slack_order(uint32_t n, const int64_t *deadline_ns /*[host] n*/, const uint32_t *steps_left /*[host] n*/,
+                           int64_t now_ns, int64_t step_ns, uint32_t m, uint32_t *order /*[host] n out*/);
 
 /* The serving loop of Sec. 3.2 (arrivals join at the next batch boundary, finished requests leave
  * at once) as one native call, for measuring a stream: query i is

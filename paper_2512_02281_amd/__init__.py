@@ -18,6 +18,7 @@ TRI_L2, TRI_IP = 0, 1
 TRI_F32, TRI_F16 = 0, 1
 TRI_CLASS_HIGH, TRI_CLASS_LOW = 0, 1
 TRI_FLAG_PROFILE, TRI_FLAG_KEEP_PROBES = 1, 2
+TRI_ORDER_FIFO, TRI_ORDER_SLACK = 0, 1
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libtrinity_ivf.so")
@@ -72,6 +73,11 @@ class tri_kernel_times(ctypes.Structure):
                 ("scan_unique_bytes", ctypes.c_uint64), ("scan_items", ctypes.c_uint64)]
 
 
+class tri_policy(ctypes.Structure):
+    _fields_ = [("high_share", ctypes.c_float), ("order_high", ctypes.c_uint32),
+                ("flush_timeout_s", ctypes.c_double), ("flush_timeout_high_s", ctypes.c_double)]
+
+
 class tri_stream_stats(ctypes.Structure):
     _fields_ = [("wall_s", ctypes.c_double), ("steps", ctypes.c_uint64), ("items", ctypes.c_uint64),
                 ("capacity", ctypes.c_uint64), ("running", ctypes.c_uint64), ("max_pending", ctypes.c_uint64)]
@@ -80,7 +86,8 @@ class tri_stream_stats(ctypes.Structure):
 EXPORTS = ["tri_pool_workspace_bytes", "tri_pool_create", "tri_pool_destroy", "ivf_build_bytes", "ivf_build",
            "ivf_export", "ivf_info", "ivf_destroy", "search_submit", "search_submit_batch", "search_submit_batch_dev",
            "search_step", "search_poll", "search_poll_batch", "search_probes", "search_cancel", "search_sync",
-           "search_run_stream", "tri_pool_kernel_times", "tri_last_error", "tri_version"]
+           "search_run_stream", "search_set_policy", "search_get_policy", "tri_policy_split", "tri_policy_slack_order",
+           "tri_pool_kernel_times", "tri_last_error", "tri_version"]
 
 
 def _load():
@@ -111,6 +118,10 @@ def _load():
     lib.search_cancel.argtypes = [vp, u64]
     lib.search_sync.argtypes = [vp]
     lib.search_run_stream.argtypes = [vp, vp, vp, u32, u32, u32, vp, vp, vp, vp, vp, P(tri_stream_stats)]
+    lib.search_set_policy.argtypes = [vp, P(tri_policy)]
+    lib.search_get_policy.argtypes = [vp, P(tri_policy), P(ctypes.c_double)]
+    lib.tri_policy_split.argtypes = [u32, u32, u32, ctypes.c_float, P(u32), P(u32)]
+    lib.tri_policy_slack_order.argtypes = [u32, vp, vp, ctypes.c_int64, ctypes.c_int64, u32, vp]
     lib.tri_pool_kernel_times.argtypes = [vp, P(tri_kernel_times), ctypes.c_int]
     lib.tri_last_error.restype = ctypes.c_char_p
     lib.tri_version.restype = ctypes.c_char_p
@@ -217,7 +228,7 @@ def search_submit(pool: int, index: int, vec: np.ndarray, k: int, nprobe: int, m
     return int(out.value)
 
 
-def make_queries(index, vecs: np.ndarray, k, nprobe, metric, klass=TRI_CLASS_LOW) -> np.ndarray:
+def make_queries(index, vecs: np.ndarray, k, nprobe, metric, klass=TRI_CLASS_LOW, deadline_ns=0) -> np.ndarray:
     """An array of tri_query records over the rows of `vecs` (which must stay alive until submitted).
     index / k / nprobe / metric / klass: scalars or per-row arrays."""
     assert vecs.flags["C_CONTIGUOUS"] and vecs.ndim == 2
@@ -226,6 +237,7 @@ def make_queries(index, vecs: np.ndarray, k, nprobe, metric, klass=TRI_CLASS_LOW
     q["index"] = index
     q["vec"] = vecs.ctypes.data + np.arange(n, dtype=np.uint64) * np.uint64(vecs.strides[0])
     q["k"], q["nprobe"], q["metric"], q["klass"] = k, nprobe, metric, klass
+    q["deadline_ns"] = deadline_ns
     return q
 
 
@@ -304,6 +316,38 @@ def search_cancel(pool: int, ticket: int) -> None:
 
 def search_sync(pool: int) -> None:
     _check(_lib.search_sync(ctypes.c_void_p(pool)), "search_sync")
+
+
+def search_set_policy(pool: int, high_share: float = 1.0, order_high: int = TRI_ORDER_FIFO,
+                      flush_timeout_s: float = 0.0, flush_timeout_high_s: float = 0.0) -> None:
+    pol = tri_policy(high_share, order_high, flush_timeout_s, flush_timeout_high_s)
+    _check(_lib.search_set_policy(ctypes.c_void_p(pool), ctypes.byref(pol)), "search_set_policy")
+
+
+def search_get_policy(pool: int):
+    """(tri_policy, mean step duration in seconds)."""
+    pol, t = tri_policy(), ctypes.c_double(0.0)
+    _check(_lib.search_get_policy(ctypes.c_void_p(pool), ctypes.byref(pol), ctypes.byref(t)), "search_get_policy")
+    return pol, float(t.value)
+
+
+def tri_policy_split(free_slots: int, n_high: int, n_low: int, high_share: float):
+    """(take_high, take_low): the admission split search_step applies at a step boundary."""
+    a, b = ctypes.c_uint32(0), ctypes.c_uint32(0)
+    _check(_lib.tri_policy_split(free_slots, n_high, n_low, high_share, ctypes.byref(a), ctypes.byref(b)), "tri_policy_split")
+    return int(a.value), int(b.value)
+
+
+def tri_policy_slack_order(deadline_ns, steps_left, now_ns: int, step_ns: int, m: Optional[int] = None) -> np.ndarray:
+    """The m (default: all) indices of least slack by ascending slack (deadline INT64_MAX = none), then the
+    other indices ascending: the order search_step applies when it admits m high-class queries."""
+    deadline_ns = np.ascontiguousarray(deadline_ns, dtype=np.int64)
+    steps_left = np.ascontiguousarray(steps_left, dtype=np.uint32)
+    order = np.zeros(deadline_ns.shape[0], dtype=np.uint32)
+    n = deadline_ns.shape[0]
+    _check(_lib.tri_policy_slack_order(n, _np_ptr(deadline_ns), _np_ptr(steps_left), now_ns, step_ns,
+                                       n if m is None else m, _np_ptr(order)), "tri_policy_slack_order")
+    return order
 
 
 def search_run_stream(pool: int, queries: np.ndarray, arrival_s: np.ndarray, stride: int, depth: int = 0,

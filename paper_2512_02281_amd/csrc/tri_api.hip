@@ -5,6 +5,8 @@
 #include "tri_common.h"
 
 #include <algorithm>
+#include <cmath>
+#include <cstdint>
 #include <cstdarg>
 #include <cstdio>
 #include <cstdlib>
@@ -41,6 +43,10 @@ int fail(int code, const char *fmt, ...)
 constexpr uint32_t RING = 4;          // steps that may be in flight before search_step waits
 constexpr uint32_t N_EV = 7;          // profile events per step
 
+inline int64_t now_ns()
+{
+    return std::chrono::duration_cast<std::chrono::nanoseconds>(std::chrono::steady_clock::now().time_since_epoch()).count();
+}
 inline uint32_t round_up(uint32_t v, uint32_t m) { return (v + m - 1) / m * m; }
 inline size_t round_up_sz(size_t v, size_t m) { return (v + m - 1) / m * m; }
 inline uint32_t esize(uint32_t dtype) { return dtype == TRI_F16 ? 2u : 4u; }
@@ -54,7 +60,9 @@ struct Ticket {
     bool cancelled = false;
     tri_index *index = nullptr;
     uint32_t k = 0, nprobe = 0, metric = 0, klass = 0;
-    uint64_t deadline = 0, tag = 0;
+    uint64_t tag = 0;
+    int64_t deadline_ns = INT64_MAX;   // absolute, on the pool's clock; INT64_MAX = none
+    int64_t submit_ns = 0;
     const void *dev_vec = nullptr;   // non-NULL: the vector is read from device memory at admission
     uint32_t slot = 0;
     uint64_t step_seq = 0;
@@ -78,6 +86,7 @@ struct StepRec {
     hipEvent_t ev[N_EV] = {};
     uint8_t *up_host = nullptr;       // pinned: upload block
     uint8_t *down_host = nullptr;     // pinned: result block, probes, step numbers
+    int64_t enqueue_ns = 0;           // when search_step enqueued it
     std::vector<uint32_t> retire;     // ticket index per retire_idx
     uint32_t n_items = 0;
     bool had_scan = false;
@@ -133,6 +142,10 @@ struct tri_pool {
     tri_kernel_times times{};
     // scratch vectors reused by search_step
     std::vector<uint32_t> order, newq;
+    // scheduling policy (Sec. 3.3) and the measured mean step duration its slack order uses
+    tri_policy policy{1.0f, TRI_ORDER_FIFO, 0.0, 0.0};
+    double mean_step_s = 0.0;
+    int64_t last_done_ns = 0;
     // search_run_stream: tickets in the order their results arrived
     bool log_done = false;
     std::vector<uint32_t> done_log;
@@ -239,6 +252,13 @@ int reap(tri_pool *P, bool block, uint32_t *finished)
             hipError_t q = hipEventQuery(R->done);
             if (q == hipErrorNotReady) break;
             if (q != hipSuccess) return fail(TRI_EHIP, "hipEventQuery -> %s", hipGetErrorString(q));
+        }
+        if (R->had_scan) {
+            // mean step duration: completion to completion while the GPU is kept busy, else enqueue to completion
+            const int64_t t = now_ns();
+            const double d = (double)(t - std::max(R->enqueue_ns, P->last_done_ns)) * 1e-9;
+            P->mean_step_s = P->mean_step_s == 0.0 ? d : 0.8 * P->mean_step_s + 0.2 * d;
+            P->last_done_ns = t;
         }
         const uint32_t kmax = P->cfg.kmax, pmax = P->cfg.nprobe_max;
         const uint32_t *blk = (const uint32_t *)R->down_host;
@@ -354,7 +374,9 @@ void enqueue_locked(tri_pool *P, const tri_query *q, tri_ticket *out)
     t.cancelled = false;
     t.index = const_cast<tri_index *>(q->index);
     t.k = q->k; t.nprobe = q->nprobe; t.metric = q->metric; t.klass = q->klass;
-    t.deadline = q->deadline_ns; t.tag = q->user_tag;
+    t.tag = q->user_tag;
+    t.submit_ns = now_ns();
+    t.deadline_ns = q->deadline_ns ? t.submit_ns + (int64_t)std::min<uint64_t>(q->deadline_ns, (uint64_t)INT64_MAX / 2) : INT64_MAX;
     t.dev_vec = nullptr;
     uint8_t *row = &P->qstore[(size_t)ti * P->max_row_bytes];
     const uint32_t es = esize(t.index->p.dtype);
@@ -799,7 +821,9 @@ extern "C" int search_submit_batch_dev(tri_pool *P, const tri_index *index, cons
         t.cancelled = false;
         t.index = const_cast<tri_index *>(index);
         t.k = k[i]; t.nprobe = nprobe[i]; t.metric = metric[i]; t.klass = klass[i];
-        t.deadline = 0; t.tag = 0;
+        t.tag = 0;
+        t.submit_ns = now_ns();
+        t.deadline_ns = INT64_MAX;
         t.dev_vec = (const uint8_t *)vecs + (size_t)i * pitch_bytes;
         P->pending[t.klass].push_back(ti);
         out[i] = ((uint64_t)t.gen << 32) | ti;
@@ -832,22 +856,43 @@ extern "C" int search_step(tri_pool *P, tri_step_stats *st)
     const uint32_t S = cfg.slots;
     TriNewDesc *desc_h = (TriNewDesc *)R.up_host;
 
-    // ---- admit: high class first, FIFO inside a class
+    // ---- admit (Sec. 3.3): the free slots are split between the classes by the reserved share, the
+    //      high class is taken in arrival or least-slack order, the low class first-in first-out
     P->newq.clear();
-    for (int klass = 0; klass < 2; ++klass) {
-        std::deque<uint32_t> &Q = P->pending[klass];
-        while (!Q.empty() && !P->free_slots.empty()) {
-            const uint32_t ti = Q.front();
-            Q.pop_front();
-            const uint32_t slot = P->free_slots.back();
-            P->free_slots.pop_back();
-            Ticket &t = P->tickets[ti];
-            t.state = T_RUNNING;
-            t.slot = slot;
-            SlotH &sl = P->slots[slot];
-            sl = SlotH{true, ti, t.nprobe, 0u, t.klass, P->admit_seq++, t.index};
-            ++P->n_running;
-            P->newq.push_back(ti);
+    {
+        uint32_t take[2] = {0, 0};
+        tri_policy_split((uint32_t)P->free_slots.size(), (uint32_t)P->pending[0].size(), (uint32_t)P->pending[1].size(),
+                         P->policy.high_share, &take[0], &take[1]);
+        std::deque<uint32_t> &H = P->pending[TRI_CLASS_HIGH];
+        if (P->policy.order_high == TRI_ORDER_SLACK && take[0] && H.size() > 1) {
+            const uint32_t n = (uint32_t)H.size();
+            std::vector<int64_t> ddl(n);
+            std::vector<uint32_t> left(n), ord(n);
+            for (uint32_t i = 0; i < n; ++i) {
+                const Ticket &t = P->tickets[H[i]];
+                ddl[i] = t.deadline_ns;
+                left[i] = cfg.lists_per_query_step ? (t.nprobe + cfg.lists_per_query_step - 1) / cfg.lists_per_query_step : 1u;
+            }
+            tri_policy_slack_order(n, ddl.data(), left.data(), now_ns(), (int64_t)(P->mean_step_s * 1e9), take[0], ord.data());
+            std::deque<uint32_t> reordered;       // admitted now: most urgent first; the rest keep their arrival order
+            for (uint32_t i = 0; i < n; ++i) reordered.push_back(H[ord[i]]);
+            H.swap(reordered);
+        }
+        for (int klass = 0; klass < 2; ++klass) {
+            std::deque<uint32_t> &Q = P->pending[klass];
+            for (uint32_t a = 0; a < take[klass]; ++a) {
+                const uint32_t ti = Q.front();
+                Q.pop_front();
+                const uint32_t slot = P->free_slots.back();
+                P->free_slots.pop_back();
+                Ticket &t = P->tickets[ti];
+                t.state = T_RUNNING;
+                t.slot = slot;
+                SlotH &sl = P->slots[slot];
+                sl = SlotH{true, ti, t.nprobe, 0u, t.klass, P->admit_seq++, t.index};
+                ++P->n_running;
+                P->newq.push_back(ti);
+            }
         }
     }
     const uint32_t n_new = (uint32_t)P->newq.size();
@@ -963,6 +1008,7 @@ extern "C" int search_step(tri_pool *P, tri_step_stats *st)
     }
     HIP_TRY(hipEventRecord(R.done, s));
     R.in_use = true;
+    R.enqueue_ns = now_ns();
     R.profiled = prof;
     R.seq = P->step_seq;
     R.n_items = n_items;
@@ -1092,6 +1138,68 @@ extern "C" int search_sync(tri_pool *P)
     return reap(P, true, nullptr);
 }
 
+// ================================================================================== policy
+extern "C" int tri_policy_split(uint32_t free_slots, uint32_t n_high, uint32_t n_low, float high_share,
+                                uint32_t *take_high, uint32_t *take_low)
+{
+    if (!take_high || !take_low) return fail(TRI_EINVAL, "NULL argument");
+    if (!(high_share >= 0.0f && high_share <= 1.0f)) return fail(TRI_EINVAL, "high_share must lie in [0, 1]");
+    // the reserved part first, then the other class up to what is left, then the high class again for the rest
+    // (a share given as a rounded float must not reserve a slot more than its decimal value says: 0.1 of 30 is 3)
+    const uint32_t reserved = (uint32_t)std::min<double>(free_slots, std::ceil((double)high_share * free_slots - 1e-4));
+    const uint32_t first_high = std::min(n_high, reserved);
+    const uint32_t low = std::min(n_low, free_slots - first_high);
+    *take_high = std::min(n_high, free_slots - low);
+    *take_low = low;
+    return TRI_OK;
+}
+
+extern "C" int tri_policy_slack_order(uint32_t n, const int64_t *deadline_ns, const uint32_t *steps_left, int64_t now_ns_,
+                                      int64_t step_ns, uint32_t m, uint32_t *order)
+{
+    if (n && (!deadline_ns || !steps_left || !order)) return fail(TRI_EINVAL, "NULL argument");
+    if (m > n) m = n;
+    std::vector<std::pair<int64_t, uint32_t>> v(n);      // (slack, index); no deadline = latest possible slack
+    for (uint32_t i = 0; i < n; ++i) {
+        const int64_t finish = now_ns_ + (int64_t)steps_left[i] * step_ns;
+        v[i] = {deadline_ns[i] == INT64_MAX ? INT64_MAX : deadline_ns[i] - finish, i};
+    }
+    // only the m most urgent need their exact order: selection is linear in n, sorting costs m log m
+    if (m < n) std::nth_element(v.begin(), v.begin() + m, v.end());
+    std::sort(v.begin(), v.begin() + m);
+    std::vector<uint8_t> chosen(n, 0);
+    for (uint32_t i = 0; i < m; ++i) {
+        order[i] = v[i].second;
+        chosen[v[i].second] = 1;
+    }
+    uint32_t w = m;
+    for (uint32_t i = 0; i < n; ++i)
+        if (!chosen[i]) order[w++] = i;
+    return TRI_OK;
+}
+
+extern "C" int search_set_policy(tri_pool *P, const tri_policy *pol)
+{
+    if (!P || !pol) return fail(TRI_EINVAL, "NULL argument");
+    if (!(pol->high_share >= 0.0f && pol->high_share <= 1.0f)) return fail(TRI_EINVAL, "high_share must lie in [0, 1]");
+    if (pol->order_high != TRI_ORDER_FIFO && pol->order_high != TRI_ORDER_SLACK)
+        return fail(TRI_EINVAL, "order_high must be TRI_ORDER_FIFO or TRI_ORDER_SLACK");
+    if (!(pol->flush_timeout_s >= 0.0) || !(pol->flush_timeout_high_s >= 0.0))
+        return fail(TRI_EINVAL, "flush time-outs must not be negative");
+    std::lock_guard<std::mutex> lk(P->mu);
+    P->policy = *pol;
+    return TRI_OK;
+}
+
+extern "C" int search_get_policy(tri_pool *P, tri_policy *pol, double *mean_step_s)
+{
+    if (!P) return fail(TRI_EINVAL, "pool is NULL");
+    std::lock_guard<std::mutex> lk(P->mu);
+    if (pol) *pol = P->policy;
+    if (mean_step_s) *mean_step_s = P->mean_step_s;
+    return TRI_OK;
+}
+
 // ================================================================================== stream driver
 // The serving loop of Sec. 3.2 as one native call: arrivals are queued when their time has come, a
 // step is enqueued whenever there is work and fewer than `depth` steps are in flight, results are
@@ -1132,7 +1240,9 @@ extern "C" int search_run_stream(tri_pool *P, const tri_query *q, const double *
         {
             std::lock_guard<std::mutex> lk(P->mu);
             const double now = elapsed();
-            while (next < n && arrival_s[next] <= now && !P->free_tickets.empty()) {
+            // (a burst is taken in in portions, so that the first step does not wait for the last copy)
+            uint32_t portion = 2 * P->cfg.slots;
+            while (next < n && arrival_s[next] <= now && !P->free_tickets.empty() && portion--) {
                 tri_ticket tk;
                 enqueue_locked(P, &q[next], &tk);
                 q_of_ticket[(uint32_t)(tk & 0xFFFFFFFFull)] = next;
@@ -1160,6 +1270,20 @@ extern "C" int search_run_stream(tri_pool *P, const tri_query *q, const double *
             const uint64_t waiting = P->pending[0].size() + P->pending[1].size();
             have_work = P->n_running > 0 || waiting > 0;
             if (waiting > acc.max_pending) acc.max_pending = waiting;
+            // flush time-outs (Sec. 3.2 / 3.3): an idle pool whose slot table could not be filled yet waits for
+            // more arrivals, but only until its oldest query -- or its oldest high-class query -- has waited long enough
+            if (P->n_running == 0 && waiting > 0 && waiting < P->cfg.slots && next < n &&
+                (P->policy.flush_timeout_s > 0.0 || P->policy.flush_timeout_high_s > 0.0)) {
+                const int64_t t = now_ns();
+                bool due = false;
+                for (int klass = 0; klass < 2; ++klass)
+                    if (!P->pending[klass].empty()) {
+                        const double waited = (double)(t - P->tickets[P->pending[klass].front()].submit_ns) * 1e-9;
+                        due = due || waited >= P->policy.flush_timeout_s ||
+                              (klass == TRI_CLASS_HIGH && waited >= P->policy.flush_timeout_high_s);
+                    }
+                if (!due) have_work = false;
+            }
         }
         if (have_work && inflight < depth) {
             tri_step_stats st;
@@ -1172,8 +1296,9 @@ extern "C" int search_run_stream(tri_pool *P, const tri_query *q, const double *
                 acc.running += st.running;
             }
         } else if (!have_work && inflight == 0 && next < n) {
-            const double wait = arrival_s[next] - elapsed();       // idle until the next arrival
-            if (wait > 200e-6) std::this_thread::sleep_for(std::chrono::duration<double>(wait - 100e-6));
+            double wait = arrival_s[next] - elapsed() - 100e-6;    // idle until the next arrival (or a flush time-out)
+            if (P->policy.flush_timeout_s > 0.0 || P->policy.flush_timeout_high_s > 0.0) wait = std::min(wait, 50e-6);
+            if (wait > 100e-6 || (wait > 0 && wait <= 50e-6)) std::this_thread::sleep_for(std::chrono::duration<double>(wait));
         } else {
             std::this_thread::yield();                              // steps in flight: their events are polled above
         }

@@ -381,6 +381,97 @@ def test_more_probed_lists_than_cached_segments():
         _say(f"many segments: parity {rep}")
 
 
+def test_scheduling_policy_reservation_slack_and_flush():
+    """The step-boundary policy of the paper's Sec. 3.3 on the GPU path: the reserved share splits the free
+    slots between the classes, the slack order admits the most urgent high-class query first, flush
+    time-outs let an idle pool collect a fuller batch -- and none of it changes any result."""
+    tri = harness.lib()
+    cfg = workloads.CONFIGS[0].scaled(n_base=8_000, n_components=32, nlist=32, n_queries=96)
+    base, queries, rows = workloads.make_config01(cfg)
+    with harness.default_pool(tri, slots=8, lists_per_query_step=4, max_dim=cfg.dim, max_outstanding=512) as pool:
+        idx = _build_f32(tri, pool, cfg, base, rows)
+        oidx = harness.oracle_index(tri, idx, base)
+        # (a) reserved share: 8 free slots, 40 + 40 waiting
+        klass = np.r_[np.full(40, tri.TRI_CLASS_HIGH), np.full(40, tri.TRI_CLASS_LOW)].astype(np.uint32)
+        q = tri.make_queries(idx, queries[:80], 10, 16, tri.TRI_L2, klass)
+        for share, want in ((0.25, (2, 6)), (1.0, (8, 0)), (0.0, (0, 8))):
+            tri.search_set_policy(pool.handle, high_share=share)
+            tickets, rc = tri.search_submit_batch(pool.handle, q)
+            st = tri.search_step(pool.handle)
+            assert (40 - st.pending_high, 40 - st.pending_low) == want, (share, st.pending_high, st.pending_low)
+            for _ in range(200):
+                st = tri.search_step(pool.handle)
+                if st.running == 0 and st.pending_high == 0 and st.pending_low == 0 and st.items == 0:
+                    break
+            tri.search_sync(pool.handle)
+            probes = [tri.search_probes(pool.handle, int(t), 16) for t in tickets]
+            ids, dist, n_out, status = tri.search_poll_batch(pool.handle, tickets, 10)
+            assert np.all(status == tri.TRI_OK)
+            harness.compare_with_oracle(oidx, base, queries[:80], 10, 16, 0, ids, dist, n_out, probes)
+        # with a share of 0.25 the low class is not starved while the high-class queue stays long
+        tri.search_set_policy(pool.handle, high_share=0.25)
+        tickets, rc = tri.search_submit_batch(pool.handle, q)
+        for step in range(12):
+            tri.search_step(pool.handle)
+        tri.search_sync(pool.handle)
+        polled = [i for i in range(40, 80) if tri.search_poll(pool.handle, int(tickets[i]), 10) is not None]
+        assert len(polled) >= 12, len(polled)             # 6 of 8 slots per generation of 4 steps
+        for _ in range(200):
+            st = tri.search_step(pool.handle)
+            if st.running == 0 and st.pending_high == 0 and st.pending_low == 0 and st.items == 0:
+                break
+        tri.search_sync(pool.handle)
+        rest = np.array([i for i in range(80) if i not in polled])
+        _, _, _, status = tri.search_poll_batch(pool.handle, tickets[rest], 10)
+        assert np.all(status == tri.TRI_OK)
+
+    # (b) slack order: one slot, three waiting high-class queries
+    with harness.default_pool(tri, slots=1, lists_per_query_step=4, max_dim=cfg.dim, max_outstanding=64) as pool:
+        idx = _build_f32(tri, pool, cfg, base, rows)
+        for order, want in ((tri.TRI_ORDER_SLACK, ["tight", "loose", "none"]), (tri.TRI_ORDER_FIFO, ["loose", "tight", "none"])):
+            tri.search_set_policy(pool.handle, order_high=order)
+            first = tri.search_submit(pool.handle, idx, queries[0], 5, 16, tri.TRI_L2, tri.TRI_CLASS_LOW)
+            tri.search_step(pool.handle)                   # occupies the only slot for four steps
+            t = {"loose": tri.search_submit(pool.handle, idx, queries[1], 5, 16, tri.TRI_L2, tri.TRI_CLASS_HIGH, 10**9),
+                 "tight": tri.search_submit(pool.handle, idx, queries[2], 5, 16, tri.TRI_L2, tri.TRI_CLASS_HIGH, 10**6),
+                 "none": tri.search_submit(pool.handle, idx, queries[3], 5, 16, tri.TRI_L2, tri.TRI_CLASS_HIGH, 0)}
+            finished = []
+            for step in range(40):
+                tri.search_step(pool.handle)
+                tri.search_sync(pool.handle)
+                for name, tk in t.items():
+                    if name not in finished and tri.search_poll(pool.handle, tk, 5) is not None:
+                        finished.append(name)
+                if len(finished) == 3:
+                    break
+            assert finished == want, (order, finished)
+            assert tri.search_poll(pool.handle, first, 5) is not None
+        pol, mean_step = tri.search_get_policy(pool.handle)
+        assert pol.order_high == tri.TRI_ORDER_FIFO and 0 < mean_step < 0.1
+
+    # (c) flush time-outs in the serving loop: sparse arrivals into an idle pool
+    with harness.default_pool(tri, slots=64, lists_per_query_step=0, max_dim=cfg.dim, max_outstanding=512) as pool:
+        idx = _build_f32(tri, pool, cfg, base, rows)
+        n = 60
+        arrival = np.arange(n) * 150e-6                     # one query every 150 us: 9 ms in all
+        klass = np.full(n, tri.TRI_CLASS_LOW, dtype=np.uint32)
+        klass[30] = tri.TRI_CLASS_HIGH
+        q = tri.make_queries(idx, queries[:n], 10, 8, tri.TRI_L2, klass)
+        out = {}
+        for name, pol in (("at once", dict()), ("global 4 ms", dict(flush_timeout_s=4e-3, flush_timeout_high_s=4e-3)),
+                          ("global 4 ms, high 0.3 ms", dict(flush_timeout_s=4e-3, flush_timeout_high_s=0.3e-3))):
+            tri.search_set_policy(pool.handle, **pol)
+            ids, dist, n_out, done_s, st, _ = tri.search_run_stream(pool.handle, q, arrival, 10)
+            out[name] = (ids, st.steps, (done_s - arrival) * 1e3)
+            _say(f"flush {name}: {st.steps} steps, mean latency {out[name][2].mean():.2f} ms, high-class query {out[name][2][30]:.2f} ms")
+        assert out["global 4 ms"][1] * 3 <= out["at once"][1]                 # far fewer, fuller steps
+        assert out["global 4 ms"][2].max() < 4.0 + 3.0                        # nobody waits much beyond the time-out
+        assert out["global 4 ms, high 0.3 ms"][2][30] < 0.3 + 1.5             # the high-class query is flushed early
+        assert out["global 4 ms, high 0.3 ms"][2][30] < out["global 4 ms"][2][30]
+        for name in out:
+            assert np.array_equal(out[name][0], out["at once"][0])            # results do not depend on the policy
+
+
 @pytest.mark.parametrize("scale", ["scaled", "full"])
 @pytest.mark.timeout(900)
 def test_config3_stream_over_two_indexes(scale):

@@ -50,6 +50,7 @@ def test_struct_layouts_match_the_header(tri):
 int main(void) {
   printf("%zu %zu %zu %zu %zu\n", sizeof(tri_pool_cfg), sizeof(ivf_params), sizeof(tri_query),
          sizeof(tri_step_stats), sizeof(tri_kernel_times));
+  printf("%zu %zu %zu\n", sizeof(tri_policy), sizeof(tri_stream_stats), offsetof(tri_policy, flush_timeout_high_s));
   printf("%zu %zu %zu %zu\n", offsetof(tri_pool_cfg, score_capacity), offsetof(tri_pool_cfg, hip_stream),
          offsetof(ivf_params, seed), offsetof(tri_query, deadline_ns));
   return 0;
@@ -62,7 +63,9 @@ int main(void) {
     sizes = [int(v) for v in out]
     assert sizes[:5] == [ctypes.sizeof(tri.tri_pool_cfg), ctypes.sizeof(tri.ivf_params), ctypes.sizeof(tri.tri_query),
                          ctypes.sizeof(tri.tri_step_stats), ctypes.sizeof(tri.tri_kernel_times)]
-    assert sizes[5:] == [tri.tri_pool_cfg.score_capacity.offset, tri.tri_pool_cfg.hip_stream.offset,
+    assert sizes[5:8] == [ctypes.sizeof(tri.tri_policy), ctypes.sizeof(tri.tri_stream_stats),
+                          tri.tri_policy.flush_timeout_high_s.offset]
+    assert sizes[8:] == [tri.tri_pool_cfg.score_capacity.offset, tri.tri_pool_cfg.hip_stream.offset,
                          tri.ivf_params.seed.offset, tri.tri_query.deadline_ns.offset]
 
 
@@ -103,6 +106,59 @@ def test_index_size_and_parameter_validation(tri):
         with pytest.raises(tri.TriError) as ei:
             tri.ivf_build_bytes(bad, nn)
         assert ei.value.status == tri.TRI_EINVAL
+
+
+def test_admission_split_properties(tri):
+    """The reserved-share rule of the step boundary (paper Sec. 3.3): the buffer is filled whenever the two
+    queues together can fill it, the high class gets at least its reserved share when it has that many
+    waiting, what one class cannot use goes to the other, and nothing is admitted that is not waiting."""
+    import numpy as np
+    rng = np.random.default_rng(5)
+    cases = [(rng.integers(0, 50), rng.integers(0, 80), rng.integers(0, 80), float(rng.choice([0, 0.1, 0.25, 0.5, 0.9, 1])))
+             for _ in range(3000)]
+    cases += [(10, 100, 100, 0.3), (10, 2, 100, 0.3), (10, 100, 3, 0.3), (0, 5, 5, 0.5), (7, 0, 0, 0.5), (7, 3, 2, 0.5)]
+    for n, nh, nl, r in cases:
+        n, nh, nl = int(n), int(nh), int(nl)
+        th, tl = tri.tri_policy_split(n, nh, nl, r)
+        assert th <= nh and tl <= nl and th + tl == min(n, nh + nl)
+        reserved = min(n, int(np.ceil(float(np.float32(r)) * n - 1e-4)))
+        assert th >= min(nh, reserved)                      # the reserved share, when the high class can use it
+        assert tl >= min(nl, n - reserved)                  # the rest, when the low class can use it
+    assert tri.tri_policy_split(10, 100, 100, 0.3) == (3, 7)
+    assert tri.tri_policy_split(10, 2, 100, 0.3) == (2, 8)      # unused reserved share goes to the low class
+    assert tri.tri_policy_split(10, 100, 3, 0.3) == (7, 3)      # unused rest goes to the high class
+    assert tri.tri_policy_split(10, 100, 100, 1.0) == (10, 0)   # the default: high class first
+    assert tri.tri_policy_split(10, 100, 100, 0.0) == (0, 10)
+    with pytest.raises(tri.TriError):
+        tri.tri_policy_split(10, 1, 1, 1.5)
+
+
+def test_slack_order_properties(tri):
+    """Least slack first, slack = deadline - (now + steps left * step time): equal step counts reduce to
+    earliest deadline first; a later deadline with many steps left can be more urgent; no deadline comes
+    last in arrival order; ties keep arrival order."""
+    import numpy as np
+    none = np.iinfo(np.int64).max
+    now, step = 1_000_000, 2_000
+    ddl = np.array([now + 50_000, now + 10_000, none, now + 30_000, none, now + 10_000], dtype=np.int64)
+    same = np.full(6, 4, dtype=np.uint32)
+    assert tri.tri_policy_slack_order(ddl, same, now, step).tolist() == [1, 5, 3, 0, 2, 4]
+    # query 0 (deadline +50 us) needs 25 steps of 2 us -> slack 0; query 3 (deadline +30 us) needs 1 -> slack 28 us
+    left = np.array([25, 4, 1, 1, 1, 4], dtype=np.uint32)
+    assert tri.tri_policy_slack_order(ddl, left, now, step).tolist() == [0, 1, 5, 3, 2, 4]
+    # against a plain restatement on random inputs
+    rng = np.random.default_rng(8)
+    for _ in range(200):
+        n = int(rng.integers(1, 40))
+        d = np.where(rng.random(n) < 0.2, none, now + rng.integers(-5_000, 100_000, size=n)).astype(np.int64)
+        e = rng.integers(1, 30, size=n).astype(np.uint32)
+        got = tri.tri_policy_slack_order(d, e, now, step)
+        slack = [float("inf") if d[i] == none else int(d[i]) - (now + int(e[i]) * step) for i in range(n)]
+        full = sorted(range(n), key=lambda i: (slack[i], i))
+        assert got.tolist() == full
+        m = int(rng.integers(0, n + 1))                     # only the m most urgent in slack order, the rest by arrival
+        assert tri.tri_policy_slack_order(d, e, now, step, m).tolist() == full[:m] + sorted(full[m:])
+    assert tri.tri_policy_slack_order(np.zeros(0, np.int64), np.zeros(0, np.uint32), now, step).shape == (0,)
 
 
 def test_product_path_never_touches_the_oracle():
