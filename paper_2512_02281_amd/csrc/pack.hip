@@ -119,7 +119,7 @@ __global__ __launch_bounds__(1024) void pack_scan_kernel(const uint32_t *__restr
                                                          uint32_t *__restrict__ stile_base,
                                                          uint64_t *__restrict__ score_base,
                                                          TriStepDev *__restrict__ step_dev,
-                                                         uint32_t *__restrict__ tile_counter)
+                                                         uint32_t *__restrict__ tile_counter, uint32_t min_chunk)
 {
     __shared__ uint32_t s_items[1024], s_tiles[1024], s_lists[1024], s_stiles[1024];
     __shared__ uint64_t s_scores[1024], s_tbytes[1024], s_ubytes[1024];
@@ -144,7 +144,7 @@ __global__ __launch_bounds__(1024) void pack_scan_kernel(const uint32_t *__restr
                 const uint32_t nt = (c + TRI_QT - 1) / TRI_QT;
                 const uint64_t bytes = (uint64_t)len * o[u].z;
                 items += c;
-                tiles += nt * o[u].w;
+                tiles += nt * ((len + tri_chunk_vecs(len, min_chunk) - 1) / tri_chunk_vecs(len, min_chunk));
                 stiles += len ? nt : 0;
                 lists += 1;
                 sc += (uint64_t)c * 2u * ((len + TRI_VB - 1) / TRI_VB * TRI_VB);
@@ -188,7 +188,7 @@ __global__ __launch_bounds__(1024) void pack_scan_kernel(const uint32_t *__restr
             score_base[g] = so;
             if (c) {
                 it += c;
-                ti += (c + TRI_QT - 1) / TRI_QT * o[u].w;
+                ti += (c + TRI_QT - 1) / TRI_QT * ((len + tri_chunk_vecs(len, min_chunk) - 1) / tri_chunk_vecs(len, min_chunk));
                 sti += len ? (c + TRI_QT - 1) / TRI_QT : 0;
                 so += (uint64_t)c * 2u * ((len + TRI_VB - 1) / TRI_VB * TRI_VB);
             }
@@ -221,7 +221,7 @@ __global__ void pack_scatter_kernel(uint32_t n_items, const uint32_t *__restrict
     item_score_off[i] = score_base[g] + (uint64_t)r * 2u * npad;
 }
 
-// (4) tiles: one thread per list of the pool-wide table.  A list longer than chunk_vecs is cut into
+// (4) tiles: one thread per list of the pool-wide table.  A list longer than its chunk length is cut into
 //     chunks; the tiles of one chunk (one per group of TRI_QT queries) are adjacent in the queue.  Every
 //     list also gets its sample tiles (first TRI_SAMPLE_VECS vectors, one per group of queries).
 __global__ void pack_tiles_kernel(uint32_t total_lists, const uint32_t *__restrict__ hist,
@@ -229,7 +229,7 @@ __global__ void pack_tiles_kernel(uint32_t total_lists, const uint32_t *__restri
                                   const uint32_t *__restrict__ stile_base, const uint64_t *__restrict__ score_base,
                                   const uint32_t *__restrict__ glist_len, const uint32_t *__restrict__ glist_voff,
                                   const uint32_t *__restrict__ glist_index, const TriIndexDev *__restrict__ indexes,
-                                  uint32_t chunk_vecs, TriTile *__restrict__ tiles, TriTile *__restrict__ stiles)
+                                  uint32_t min_chunk, TriTile *__restrict__ tiles, TriTile *__restrict__ stiles)
 {
     const uint32_t g = blockIdx.x * blockDim.x + threadIdx.x;
     if (g >= total_lists) return;
@@ -239,6 +239,7 @@ __global__ void pack_tiles_kernel(uint32_t total_lists, const uint32_t *__restri
     const TriIndexDev &ix = indexes[glist_index[g]];
     const uint32_t npad = (len + TRI_VB - 1) / TRI_VB * TRI_VB;
     const uint32_t nt = (c + TRI_QT - 1) / TRI_QT;
+    const uint32_t chunk_vecs = tri_chunk_vecs(len, min_chunk);
     const uint32_t nchunks = (len + chunk_vecs - 1) / chunk_vecs;
     const uint32_t voff = glist_voff[g];
     TriTile tl;
@@ -276,7 +277,7 @@ __global__ void pack_tiles_kernel(uint32_t total_lists, const uint32_t *__restri
 }
 
 hipError_t tri_launch_pack(const TriLaunchCtx &c, const TriDevWs &ws, const TriPlanEntry *plan_dev, uint32_t n_plan,
-                           uint32_t n_items, uint32_t total_lists, uint32_t n_order, uint32_t chunk_vecs)
+                           uint32_t n_items, uint32_t total_lists, uint32_t n_order, uint32_t min_chunk)
 {
     if (n_items == 0 || total_lists == 0) return hipSuccess;
     hipError_t e = tri_launch_fill_u32(c.stream, ws.hist, 0u, total_lists);
@@ -285,12 +286,12 @@ hipError_t tri_launch_pack(const TriLaunchCtx &c, const TriDevWs &ws, const TriP
                        n_items, ws.slot_meta, ws.indexes, ws.probe, c.nprobe_max, ws.item_glist, ws.item_slot,
                        ws.item_rank, ws.hist);
     hipLaunchKernelGGL(pack_scan_kernel, dim3(1), dim3(1024), 0, c.stream, ws.hist, n_order, ws.glist_order, ws.list_start,
-                       ws.tile_base, ws.stile_base, ws.score_base, ws.step_dev, ws.tile_counter);
+                       ws.tile_base, ws.stile_base, ws.score_base, ws.step_dev, ws.tile_counter, min_chunk);
     hipLaunchKernelGGL(pack_scatter_kernel, dim3((n_items + 255) / 256), dim3(256), 0, c.stream, n_items,
                        ws.item_glist, ws.item_slot, ws.item_rank, ws.list_start, ws.score_base, ws.glist_len,
                        ws.sorted_slot, ws.item_score_off, ws.item_sorted_pos);
     hipLaunchKernelGGL(pack_tiles_kernel, dim3((total_lists + 255) / 256), dim3(256), 0, c.stream, total_lists,
                        ws.hist, ws.list_start, ws.tile_base, ws.stile_base, ws.score_base, ws.glist_len, ws.glist_voff,
-                       ws.glist_index, ws.indexes, chunk_vecs, ws.tiles, ws.stiles);
+                       ws.glist_index, ws.indexes, min_chunk, ws.tiles, ws.stiles);
     return hipGetLastError();
 }

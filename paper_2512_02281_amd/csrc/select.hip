@@ -626,7 +626,7 @@ __global__ __launch_bounds__(TRI_SEL_THREADS) void slot_merge_kernel(
     const TriPlanEntry *__restrict__ plan, const TriSlotMeta *__restrict__ slot_meta,
     const TriIndexDev *__restrict__ indexes, const uint32_t *__restrict__ item_glist,
     const uint64_t *__restrict__ item_score_off, const uint32_t *__restrict__ item_sorted_pos,
-    const uint32_t *__restrict__ surv_count, uint32_t chunk_vecs, const uint32_t *__restrict__ glist_len,
+    const uint32_t *__restrict__ surv_count, uint32_t min_chunk, const uint32_t *__restrict__ glist_len,
     const uint32_t *__restrict__ glist_voff, const float *__restrict__ cand, float *__restrict__ topk_score,
     uint32_t *__restrict__ topk_id, uint32_t *__restrict__ topk_count, uint32_t kmax,
     uint32_t *__restrict__ res_block, const uint32_t *__restrict__ probe, uint32_t nprobe_max,
@@ -646,6 +646,7 @@ __global__ __launch_bounds__(TRI_SEL_THREADS) void slot_merge_kernel(
     auto seg_of = [&](uint32_t s) {
         const uint32_t it = e.item_base + s / TRI_TILES_PER_ITEM, ch = s % TRI_TILES_PER_ITEM;
         const uint32_t g = item_glist[it];
+        const uint32_t chunk_vecs = tri_chunk_vecs(glist_len[g], min_chunk);
         const uint32_t nch = (glist_len[g] + chunk_vecs - 1) / chunk_vecs;
         if (ch >= nch) return SelSeg{0u, 0u, 0u, 0u};
         return SelSeg{(uint32_t)(item_score_off[it] / 2u) + ch * chunk_vecs,
@@ -678,11 +679,11 @@ __global__ __launch_bounds__(TRI_SEL_THREADS) void slot_merge_kernel(
 }
 
 hipError_t tri_launch_merge(const TriLaunchCtx &c, const TriDevWs &ws, const TriPlanEntry *plan_dev, uint32_t n_plan,
-                            bool keep_probes, uint32_t chunk_vecs)
+                            bool keep_probes, uint32_t min_chunk)
 {
     if (n_plan == 0) return hipSuccess;
     hipLaunchKernelGGL(slot_merge_kernel, dim3(n_plan), dim3(TRI_SEL_THREADS), 0, c.stream, plan_dev, ws.slot_meta,
-                       ws.indexes, ws.item_glist, ws.item_score_off, ws.item_sorted_pos, ws.surv_count, chunk_vecs,
+                       ws.indexes, ws.item_glist, ws.item_score_off, ws.item_sorted_pos, ws.surv_count, min_chunk,
                        ws.glist_len, ws.glist_voff, ws.scores, ws.topk_score, ws.topk_id, ws.topk_count, c.kmax,
                        ws.res_block, ws.probe, c.nprobe_max, keep_probes ? ws.res_probes : (uint32_t *)nullptr);
     return hipGetLastError();

@@ -117,7 +117,6 @@ struct tri_pool {
     uint32_t attached_row_bytes = 128;   // widest row among the attached indexes (sizes the scan kernel's LDS)
     uint32_t scan_class_mask = 0;        // scan kernel variants the attached indexes need
     uint32_t n_order = 0;                // attached lists (entries of the device-side scan order)
-    uint32_t chunk_vecs = 1024;          // lists longer than this are scanned as several tiles (at most 4)
     uint64_t score_capacity = 0;
     size_t upload_bytes = 0, down_bytes = 0;
     size_t down_probe_off = 0, down_step_off = 0;
@@ -319,10 +318,6 @@ int upload_scan_order(tri_pool *P)
     std::stable_sort(v.begin(), v.end(), [](const std::pair<uint64_t, uint32_t> &a, const std::pair<uint64_t, uint32_t> &b) {
         return a.first > b.first;
     });
-    uint32_t longest = 0;
-    for (tri_index *ix : P->indexes)
-        if (ix) longest = std::max(longest, ix->max_list_len);
-    P->chunk_vecs = std::max(1024u, round_up((longest + TRI_TILES_PER_ITEM - 1) / TRI_TILES_PER_ITEM, TRI_VB));
     // per entry everything the per-step prefix sums need, so that they read this array front to back
     std::vector<uint4> order(v.size());
     uint32_t extent = 0;
@@ -336,7 +331,7 @@ int upload_scan_order(tri_pool *P)
         const uint32_t g = v[i].second;
         const tri_index *ix = owner[g];
         const uint32_t len = ix->list_len[g - ix->list_base];
-        order[i] = make_uint4(g, len, ix->row_bytes, (len + P->chunk_vecs - 1) / P->chunk_vecs);
+        order[i] = make_uint4(g, len, ix->row_bytes, 0u);
     }
     if (!order.empty())
         HIP_TRY(hipMemcpy(P->ws.glist_order, order.data(), order.size() * sizeof(uint4), hipMemcpyHostToDevice));
@@ -984,7 +979,9 @@ extern "C" int search_step(tri_pool *P, tri_step_stats *st)
         a = b;
     }
     if (prof) HIP_TRY(hipEventRecord(R.ev[2], s));
-    HIP_TRY(tri_launch_pack(P->ctx, P->ws, plan_d, n_plan, n_items, P->total_lists, P->n_order, P->chunk_vecs));
+    // chunk length floor of this step: with fewer tiles than a few per wavefront, cut the lists finer
+    const uint32_t min_chunk = n_items > 8u * P->ctx.n_cu ? 1024u : 64u;
+    HIP_TRY(tri_launch_pack(P->ctx, P->ws, plan_d, n_plan, n_items, P->total_lists, P->n_order, min_chunk));
     if (prof) HIP_TRY(hipEventRecord(R.ev[3], s));
     // thresholds: score a sample of every probed list, k-th best of each slot's sample
     if (n_items) HIP_TRY(tri_launch_scan(P->ctx, P->ws, P->attached_row_bytes, P->scan_class_mask, true));
@@ -992,7 +989,7 @@ extern "C" int search_step(tri_pool *P, tri_step_stats *st)
     if (prof) HIP_TRY(hipEventRecord(R.ev[4], s));
     if (n_items) HIP_TRY(tri_launch_scan(P->ctx, P->ws, P->attached_row_bytes, P->scan_class_mask, false));
     if (prof) HIP_TRY(hipEventRecord(R.ev[5], s));
-    HIP_TRY(tri_launch_merge(P->ctx, P->ws, plan_d, n_plan, (cfg.flags & TRI_FLAG_KEEP_PROBES) != 0, P->chunk_vecs));
+    HIP_TRY(tri_launch_merge(P->ctx, P->ws, plan_d, n_plan, (cfg.flags & TRI_FLAG_KEEP_PROBES) != 0, min_chunk));
     // (the result copy stays on the pool's stream: on a second stream it ran beside the next step's
     // scan and slowed that by far more than the transfer takes)
     if (n_retire) {

@@ -118,7 +118,7 @@ struct TriDevWs {
     uint32_t *glist_voff;     // [max_total_lists] first stored position inside its index
     uint32_t *glist_index;    // [max_total_lists]
     uint4 *glist_order;       // [max_total_lists] attached lists by descending byte length (scan order):
-                              //   {pool-wide list number, length, row bytes, chunks}
+                              //   {pool-wide list number, length, row bytes, 0}
     // per-step upload block (device copy)
     uint8_t *upload;          // upload_bytes
     // coarse ranking
@@ -167,12 +167,23 @@ hipError_t tri_launch_coarse_select(const TriLaunchCtx &c, const TriDevWs &ws, c
                                     uint32_t first_new, uint32_t m, uint32_t nlist, uint32_t ldc);
 hipError_t tri_launch_pack(const TriLaunchCtx &c, const TriDevWs &ws, const TriPlanEntry *plan_dev,
                            uint32_t n_plan, uint32_t n_items, uint32_t total_lists, uint32_t n_order,
-                           uint32_t chunk_vecs);
+                           uint32_t min_chunk);
 hipError_t tri_launch_scan(const TriLaunchCtx &c, const TriDevWs &ws, uint32_t max_row_bytes, uint32_t class_mask,
                            bool sample);
 hipError_t tri_launch_threshold(const TriLaunchCtx &c, const TriDevWs &ws, const TriPlanEntry *plan_dev,
                                 uint32_t n_plan);
 #define TRI_TILES_PER_ITEM 4   // tile capacity = 4 W: a list is cut into at most 4 chunks
+
+// Chunking of a list for the scan: at most TRI_TILES_PER_ITEM chunks of equal length (a multiple of 32
+// vectors), none shorter than min_chunk.  min_chunk is chosen per step: large when the step has far more
+// tiles than wavefronts anyway (fewer tiles, fewer query loads), small when tiles are few, so that one
+// long list does not keep a single wavefront busy for the whole launch.
+__host__ __device__ inline uint32_t tri_chunk_vecs(uint32_t len, uint32_t min_chunk)
+{
+    uint32_t c = (len + TRI_TILES_PER_ITEM - 1) / TRI_TILES_PER_ITEM;
+    c = (c + TRI_VB - 1) / TRI_VB * TRI_VB;
+    return c > min_chunk ? c : min_chunk;
+}
 
 // Which scan kernel serves an index: 5 classes per storage type (other, 512, 1024, 1536, 2048 bytes per row).
 __host__ __device__ inline uint32_t tri_scan_class(uint32_t dtype, uint32_t row_bytes)
@@ -181,7 +192,7 @@ __host__ __device__ inline uint32_t tri_scan_class(uint32_t dtype, uint32_t row_
     return dtype * 5 + (special ? row_bytes / 512 : 0);
 }
 hipError_t tri_launch_merge(const TriLaunchCtx &c, const TriDevWs &ws, const TriPlanEntry *plan_dev,
-                            uint32_t n_plan, bool keep_probes, uint32_t chunk_vecs);
+                            uint32_t n_plan, bool keep_probes, uint32_t min_chunk);
 
 // ---- index construction helpers ------------------------------------------------------------
 hipError_t tri_build_pad_rows(hipStream_t s, int dtype, const void *src, uint32_t dim, uint64_t src_pitch_elems,
