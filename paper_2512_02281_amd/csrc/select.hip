@@ -279,27 +279,19 @@ __device__ __forceinline__ uint32_t sel_key_of(uint32_t x) { return x; }
 __device__ __forceinline__ uint32_t sel_key_of(uint64_t x) { return (uint32_t)(x >> 32); }
 
 // Bucket of a key: monotone in the key (conversions, the product with a positive factor and the
-// truncation all preserve order), 0 at or below kmin, SEL_BINS - 1 at or above kmax.
+// truncation all preserve order), 0 at or below kmin, SEL_BINS - 1 at or above the largest key.
 __device__ __forceinline__ uint32_t sel_bucket(uint32_t key, uint32_t kmin, float scale)
 {
     if (key <= kmin) return 0u;
     return (uint32_t)fminf((float)(key - kmin) * scale, (float)(SEL_BINS - 1));
 }
 
-// Smallest and largest key among a[0..n) (keys equal to all-ones, the padding value, are ignored) and
-// a zeroed histogram.  Ends with a barrier.  Returns the scale of sel_bucket.
-template <typename T>
-__device__ __forceinline__ float sel_range(SelShared &sh, const T *a, uint32_t n, uint32_t &kmin)
+// Bucket range from the smallest and largest key (every thread passes those of its own keys; all-ones,
+// the padding value, must be left out).  Also zeroes the histogram.  Ends with a barrier.  Returns the
+// scale of sel_bucket.
+__device__ __forceinline__ float sel_range(SelShared &sh, uint32_t lo, uint32_t hi, uint32_t &kmin)
 {
     const uint32_t lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    uint32_t lo = 0xFFFFFFFFu, hi = 0u;
-    for (uint32_t i = threadIdx.x; i < n; i += TRI_SEL_THREADS) {
-        const uint32_t key = sel_key_of(a[i]);
-        if (key != 0xFFFFFFFFu) {
-            lo = key < lo ? key : lo;
-            hi = key > hi ? key : hi;
-        }
-    }
 #pragma unroll
     for (int d = 32; d > 0; d >>= 1) {
         const uint32_t l2 = (uint32_t)__shfl_xor((int)lo, d, 64), h2 = (uint32_t)__shfl_xor((int)hi, d, 64);
@@ -325,8 +317,15 @@ __device__ __forceinline__ float sel_range(SelShared &sh, const T *a, uint32_t n
 // which at least m are not the padding value all-ones).  Uses sh.hist.
 __device__ uint32_t sel_keys_threshold(SelShared &sh, const uint32_t *a, uint32_t n, uint32_t m)
 {
-    uint32_t kmin;
-    const float scale = sel_range(sh, a, n, kmin);
+    uint32_t kmin, lo = 0xFFFFFFFFu, hi = 0u;
+    for (uint32_t i = threadIdx.x; i < n; i += TRI_SEL_THREADS) {
+        const uint32_t key = a[i];
+        if (key != 0xFFFFFFFFu) {
+            lo = key < lo ? key : lo;
+            hi = key > hi ? key : hi;
+        }
+    }
+    const float scale = sel_range(sh, lo, hi, kmin);
     for (uint32_t i = threadIdx.x; i < n; i += TRI_SEL_THREADS) atomicAdd(&sh.hist[sel_bucket(a[i], kmin, scale)], 1u);
     if (threadIdx.x == 0) sh.tmax = 0u;
     __syncthreads();
@@ -381,8 +380,13 @@ __device__ const uint64_t *sel_pool_topk(SelShared &sh, uint32_t n, uint32_t k)
         return sh.small;
     }
     if (k < n && k < SEL_SMALL) {
-        uint32_t kmin;
-        const float scale = sel_range(sh, sh.pool, n, kmin);
+        uint32_t kmin, lo = 0xFFFFFFFFu, hi = 0u;
+        for (uint32_t i = threadIdx.x; i < n; i += TRI_SEL_THREADS) {
+            const uint32_t key = sel_key_of(sh.pool[i]);
+            lo = key < lo ? key : lo;
+            hi = key > hi ? key : hi;
+        }
+        const float scale = sel_range(sh, lo, hi, kmin);
         for (uint32_t i = threadIdx.x; i < n; i += TRI_SEL_THREADS)
             atomicAdd(&sh.hist[sel_bucket(sel_key_of(sh.pool[i]), kmin, scale)], 1u);
         if (threadIdx.x == 0) sh.cnt = 0;
@@ -534,19 +538,74 @@ __device__ const uint64_t *sel_block_topk(SelShared &sh, const SelSrc &src, SegF
 
 // ------------------------------------------------------------------------------------------------
 // Coarse selection: probe list of each newly admitted query = the nprobe best centroids, best
-// first, ties -> smaller centroid number.
+// first, ties -> smaller centroid number.  Rows of up to CSEL_PER * 256 scores take a one-pass path
+// (the row sits in registers while the bucket cut is made); longer rows, and rows in which the cut
+// fails to isolate a small set (masses of equal scores), go through the general selection.
+#define CSEL_PER 64        // scores per thread the fast path holds in registers: rows of up to 16384 centroids
+
 __global__ __launch_bounds__(TRI_SEL_THREADS) void coarse_select_kernel(
     const float *__restrict__ scores, uint32_t ldc, uint32_t nlist, const TriNewDesc *__restrict__ desc,
     uint32_t first_new, uint32_t *__restrict__ probe, uint32_t nprobe_max)
 {
     __shared__ SelShared sh;
     const TriNewDesc d = desc[first_new + blockIdx.x];
-    const SelSrc src = {nullptr, nullptr, scores + (size_t)blockIdx.x * ldc, nullptr, 0u, nlist};
+    const float *row = scores + (size_t)blockIdx.x * ldc;
+    uint32_t *dst = probe + (size_t)d.slot * nprobe_max;
+    const uint32_t tid = threadIdx.x;
+    if (nlist <= CSEL_PER * TRI_SEL_THREADS && d.nprobe < nlist) {
+        // ---- fast path: the whole row is read once, into registers, and cut by buckets from there
+        // (loads through a descriptor that ends with the row: all 64 are in flight together, no branches)
+        const __amdgpu_buffer_rsrc_t rrs = __builtin_amdgcn_make_buffer_rsrc((void *)row, 0, nlist * 4u, 0x00020000);
+        uint32_t key[CSEL_PER];
+#pragma unroll
+        for (int u = 0; u < CSEL_PER; ++u)
+            key[u] = __builtin_amdgcn_raw_buffer_load_b32(rrs, (u * TRI_SEL_THREADS + tid) * 4u, 0, 0);
+#pragma unroll
+        for (int u = 0; u < CSEL_PER; ++u)                         // (all-ones: padding, ignored below)
+            key[u] = u * TRI_SEL_THREADS + tid < nlist ? sel_key(__uint_as_float(key[u]), d.metric) : 0xFFFFFFFFu;
+        if (tid == 0) sh.cnt = 0;
+        uint32_t kmin, lo = 0xFFFFFFFFu, hi = 0u;
+#pragma unroll
+        for (int u = 0; u < CSEL_PER; ++u)
+            if (key[u] != 0xFFFFFFFFu) {
+                lo = key[u] < lo ? key[u] : lo;
+                hi = key[u] > hi ? key[u] : hi;
+            }
+        const float scale = sel_range(sh, lo, hi, kmin);
+#pragma unroll
+        for (int u = 0; u < CSEL_PER; ++u)
+            if (u * TRI_SEL_THREADS + tid < nlist) atomicAdd(&sh.hist[sel_bucket(key[u], kmin, scale)], 1u);
+        __syncthreads();
+        sel_find_digit(sh, SEL_BINS, d.nprobe);
+        const uint32_t B = sh.digit;
+        const uint32_t c_le = d.nprobe - sh.need + sh.count;     // centroids in buckets <= B
+        __syncthreads();                                          // the histogram is dead: sh.small reuses it
+        if (c_le <= SEL_SMALL) {
+#pragma unroll
+            for (int u = 0; u < CSEL_PER; ++u) {
+                const uint32_t e = u * TRI_SEL_THREADS + tid;
+                const bool take = e < nlist && sel_bucket(key[u], kmin, scale) <= B;
+                const uint32_t pos = sel_append_pos(take, &sh.cnt);
+                if (take) sh.small[pos] = ((uint64_t)key[u] << 32) | e;
+            }
+            __syncthreads();
+            const uint64_t *best;
+            if (c_le <= SEL_RANK_MAX) {
+                sel_rank_sort(sh.small, c_le, sh.pool);
+                best = sh.pool;
+            } else {
+                sel_bitonic(sh.small, c_le);
+                best = sh.small;
+            }
+            for (uint32_t i = tid; i < d.nprobe; i += TRI_SEL_THREADS) dst[i] = (uint32_t)(best[i] & 0xFFFFFFFFu);
+            return;                                               // (uniform: c_le comes from shared memory)
+        }
+    }
+    const SelSrc src = {nullptr, nullptr, row, nullptr, 0u, nlist};
     auto seg_of = [&](uint32_t) { return SelSeg{0u, 0u, 0u, 0u}; };
     uint32_t n;
     const uint64_t *best = sel_block_topk(sh, src, seg_of, d.nprobe, d.metric, &n);
-    uint32_t *dst = probe + (size_t)d.slot * nprobe_max;
-    for (uint32_t i = threadIdx.x; i < n; i += TRI_SEL_THREADS) dst[i] = (uint32_t)(best[i] & 0xFFFFFFFFu);
+    for (uint32_t i = tid; i < n; i += TRI_SEL_THREADS) dst[i] = (uint32_t)(best[i] & 0xFFFFFFFFu);
 }
 
 hipError_t tri_launch_coarse_select(const TriLaunchCtx &c, const TriDevWs &ws, const TriNewDesc *desc_dev,
