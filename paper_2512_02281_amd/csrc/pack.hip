@@ -5,6 +5,8 @@
 // up to TRI_QT queries.
 #include "tri_common.h"
 
+#include <algorithm>
+
 // ---------------------------------------------------------------------------------------- fill
 __global__ void fill_u32_kernel(uint32_t *p, uint32_t v, size_t n)
 {
@@ -108,10 +110,16 @@ __global__ void pack_emit_kernel(const TriPlanEntry *__restrict__ plan, uint32_t
     item_rank[i] = atomicAdd(&hist[g], 1u);
 }
 
-// (2) scan: one workgroup.  Exclusive prefix sums, taken over the attached lists in the order of
-//     descending byte length (so the longest tiles are dealt out first and the step ends on the
-//     shortest), of: items per list (-> list_start), tiles per list (-> tile_base), padded scores
-//     per list (-> score_base).  Also the step totals and the reset of the work-queue heads.
+// (2) scan.  Exclusive prefix sums, taken over the attached lists in the order of descending byte
+//     length (so the longest tiles are dealt out first and the step ends on the shortest), of: items
+//     per list (-> list_start), tiles per list (-> tile_base), padded scores per list (-> score_base).
+//     Also the step totals and the reset of the work-queue heads.  Up to PACK_SCAN_BLOCKS workgroups,
+//     each over a contiguous span of the order, in two launches: FINAL = false leaves every span's
+//     totals in block_tot, FINAL = true adds the totals of the spans before its own and writes.
+#define PACK_SCAN_BLOCKS 16
+#define PACK_SCAN_SUMS 8      // values per span in block_tot (7 used)
+
+template <bool FINAL>
 __global__ __launch_bounds__(1024) void pack_scan_kernel(const uint32_t *__restrict__ hist, uint32_t n_order,
                                                          const uint4 *__restrict__ order,
                                                          uint32_t *__restrict__ list_start,
@@ -119,13 +127,16 @@ __global__ __launch_bounds__(1024) void pack_scan_kernel(const uint32_t *__restr
                                                          uint32_t *__restrict__ stile_base,
                                                          uint64_t *__restrict__ score_base,
                                                          TriStepDev *__restrict__ step_dev,
-                                                         uint32_t *__restrict__ tile_counter, uint32_t min_chunk)
+                                                         uint32_t *__restrict__ tile_counter, uint32_t min_chunk,
+                                                         uint64_t *__restrict__ block_tot)
 {
     __shared__ uint32_t s_items[1024], s_tiles[1024], s_lists[1024], s_stiles[1024];
     __shared__ uint64_t s_scores[1024], s_tbytes[1024], s_ubytes[1024];
     const uint32_t t = threadIdx.x;
-    const uint32_t per = (n_order + 1023) / 1024;
-    const uint32_t i0 = min(t * per, n_order), i1 = min(i0 + per, n_order);
+    const uint32_t span = (n_order + gridDim.x - 1) / gridDim.x;
+    const uint32_t s0 = min(blockIdx.x * span, n_order), s1 = min(s0 + span, n_order);
+    const uint32_t per = (span + 1023) / 1024;
+    const uint32_t i0 = min(s0 + t * per, s1), i1 = min(i0 + per, s1);
     uint32_t items = 0, tiles = 0, lists = 0, stiles = 0;
     uint64_t sc = 0, tb = 0, ub = 0;
     // (entries {list, length, row bytes, chunks} are static; only the item counts are gathered, several at once)
@@ -169,8 +180,21 @@ __global__ __launch_bounds__(1024) void pack_scan_kernel(const uint32_t *__restr
         s_scores[t] += x; s_tbytes[t] += y; s_ubytes[t] += z;
         __syncthreads();
     }
-    uint32_t it = s_items[t] - items, ti = s_tiles[t] - tiles, sti = s_stiles[t] - stiles;
-    uint64_t so = s_scores[t] - sc;
+    if (!FINAL) {
+        if (t == 1023) {
+            uint64_t *o = block_tot + blockIdx.x * PACK_SCAN_SUMS;
+            o[0] = s_items[t]; o[1] = s_tiles[t]; o[2] = s_lists[t]; o[3] = s_stiles[t];
+            o[4] = s_scores[t]; o[5] = s_tbytes[t]; o[6] = s_ubytes[t];
+        }
+        return;
+    }
+    uint64_t base[PACK_SCAN_SUMS - 1] = {};      // totals of the spans before this one
+    for (uint32_t b = 0; b < blockIdx.x; ++b)
+#pragma unroll
+        for (int v = 0; v < PACK_SCAN_SUMS - 1; ++v) base[v] += block_tot[b * PACK_SCAN_SUMS + v];
+    uint32_t it = (uint32_t)base[0] + s_items[t] - items, ti = (uint32_t)base[1] + s_tiles[t] - tiles,
+             sti = (uint32_t)base[3] + s_stiles[t] - stiles;
+    uint64_t so = base[4] + s_scores[t] - sc;
     for (uint32_t ib = i0; ib < i1; ib += 8) {
         uint4 o[8];
         uint32_t cnt[8];
@@ -194,13 +218,13 @@ __global__ __launch_bounds__(1024) void pack_scan_kernel(const uint32_t *__restr
             }
         }
     }
-    if (t == 1023) {
-        step_dev->n_tiles = s_tiles[t];
-        step_dev->n_sample_tiles = s_stiles[t];
-        step_dev->n_lists_touched = s_lists[t];
-        step_dev->total_scores = s_scores[t];
-        step_dev->tile_vec_bytes = s_tbytes[t];
-        step_dev->unique_vec_bytes = s_ubytes[t];
+    if (t == 1023 && blockIdx.x == gridDim.x - 1) {
+        step_dev->n_tiles = (uint32_t)base[1] + s_tiles[t];
+        step_dev->n_sample_tiles = (uint32_t)base[3] + s_stiles[t];
+        step_dev->n_lists_touched = (uint32_t)base[2] + s_lists[t];
+        step_dev->total_scores = base[4] + s_scores[t];
+        step_dev->tile_vec_bytes = base[5] + s_tbytes[t];
+        step_dev->unique_vec_bytes = base[6] + s_ubytes[t];
         for (uint32_t k = 0; k < 2 * TRI_SCAN_CLASSES; ++k) tile_counter[k] = 0;
     }
 }
@@ -285,8 +309,14 @@ hipError_t tri_launch_pack(const TriLaunchCtx &c, const TriDevWs &ws, const TriP
     hipLaunchKernelGGL(pack_emit_kernel, dim3((n_items + 255) / 256), dim3(256), 0, c.stream, plan_dev, n_plan,
                        n_items, ws.slot_meta, ws.indexes, ws.probe, c.nprobe_max, ws.item_glist, ws.item_slot,
                        ws.item_rank, ws.hist);
-    hipLaunchKernelGGL(pack_scan_kernel, dim3(1), dim3(1024), 0, c.stream, ws.hist, n_order, ws.glist_order, ws.list_start,
-                       ws.tile_base, ws.stile_base, ws.score_base, ws.step_dev, ws.tile_counter, min_chunk);
+    const uint32_t nb = std::min<uint32_t>(PACK_SCAN_BLOCKS, (n_order + 1023) / 1024);
+    if (nb > 1)
+        hipLaunchKernelGGL(pack_scan_kernel<false>, dim3(nb), dim3(1024), 0, c.stream, ws.hist, n_order, ws.glist_order,
+                           ws.list_start, ws.tile_base, ws.stile_base, ws.score_base, ws.step_dev, ws.tile_counter,
+                           min_chunk, ws.pack_tot);
+    hipLaunchKernelGGL(pack_scan_kernel<true>, dim3(nb ? nb : 1), dim3(1024), 0, c.stream, ws.hist, n_order, ws.glist_order,
+                       ws.list_start, ws.tile_base, ws.stile_base, ws.score_base, ws.step_dev, ws.tile_counter, min_chunk,
+                       ws.pack_tot);
     hipLaunchKernelGGL(pack_scatter_kernel, dim3((n_items + 255) / 256), dim3(256), 0, c.stream, n_items,
                        ws.item_glist, ws.item_slot, ws.item_rank, ws.list_start, ws.score_base, ws.glist_len,
                        ws.sorted_slot, ws.item_score_off, ws.item_sorted_pos);

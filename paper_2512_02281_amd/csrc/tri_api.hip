@@ -177,6 +177,7 @@ size_t carve(const tri_pool_cfg &c, uint32_t max_row_bytes, uint32_t coarse_rows
     CARVE(glist_voff, uint32_t *, G * 4)
     CARVE(glist_index, uint32_t *, G * 4)
     CARVE(glist_order, uint4 *, G * 16)
+    CARVE(pack_tot, uint64_t *, 16 * 8 * 8)
     CARVE(upload, uint8_t *, upload_bytes)
     CARVE(coarse_scores, float *, (size_t)coarse_rows * coarse_ldc * 4)
     CARVE(item_glist, uint32_t *, W * 4)
