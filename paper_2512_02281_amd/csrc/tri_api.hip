@@ -86,6 +86,7 @@ struct StepRec {
     hipEvent_t ev[N_EV] = {};
     uint8_t *up_host = nullptr;       // pinned: upload block
     uint8_t *down_host = nullptr;     // pinned: result block, probes, step numbers
+    uint8_t *down_dev = nullptr;      // the same memory as the GPU addresses it
     int64_t enqueue_ns = 0;           // when search_step enqueued it
     std::vector<uint32_t> retire;     // ticket index per retire_idx
     uint32_t n_items = 0;
@@ -199,8 +200,7 @@ size_t carve(const tri_pool_cfg &c, uint32_t max_row_bytes, uint32_t coarse_rows
     CARVE(thr_key, uint32_t *, S * 4)
     CARVE(step_dev, TriStepDev *, 256)
     CARVE(scores, float *, (size_t)score_capacity * 4)
-    CARVE(res_block, uint32_t *, S * (1 + 2 * (size_t)c.kmax) * 4)
-    CARVE(res_probes, uint32_t *, S * (size_t)c.nprobe_max * 4)
+    // (res_block / res_probes point into the pinned host block of the step in flight: set per step)
 #undef CARVE
     return o;
 }
@@ -436,6 +436,8 @@ extern "C" int tri_pool_create(const tri_pool_cfg *cfg, void *dev_ws, size_t dev
         StepRec &R = P->ring[i];
         R.up_host = P->pinned + i * per;
         R.down_host = R.up_host + round_up_sz(up, 256);
+        e = hipHostGetDevicePointer((void **)&R.down_dev, R.down_host, 0);
+        if (e != hipSuccess) { tri_pool_destroy(P); return fail(TRI_EHIP, "hipHostGetDevicePointer -> %s", hipGetErrorString(e)); }
         e = hipEventCreateWithFlags(&R.done, hipEventDisableTiming);
         for (uint32_t j = 0; j < N_EV && e == hipSuccess; ++j) e = hipEventCreate(&R.ev[j]);
         if (e != hipSuccess) { tri_pool_destroy(P); return fail(TRI_EHIP, "hipEventCreate -> %s", hipGetErrorString(e)); }
@@ -990,16 +992,14 @@ extern "C" int search_step(tri_pool *P, tri_step_stats *st)
     if (prof) HIP_TRY(hipEventRecord(R.ev[4], s));
     if (n_items) HIP_TRY(tri_launch_scan(P->ctx, P->ws, P->attached_row_bytes, P->scan_class_mask, false));
     if (prof) HIP_TRY(hipEventRecord(R.ev[5], s));
-    HIP_TRY(tri_launch_merge(P->ctx, P->ws, plan_d, n_plan, (cfg.flags & TRI_FLAG_KEEP_PROBES) != 0, min_chunk));
-    // (the result copy stays on the pool's stream: on a second stream it ran beside the next step's
-    // scan and slowed that by far more than the transfer takes)
-    if (n_retire) {
-        HIP_TRY(hipMemcpyAsync(R.down_host, P->ws.res_block, (size_t)n_retire * (1 + 2 * (size_t)cfg.kmax) * 4,
-                               hipMemcpyDeviceToHost, s));
-        if (cfg.flags & TRI_FLAG_KEEP_PROBES)
-            HIP_TRY(hipMemcpyAsync(R.down_host + P->down_probe_off, P->ws.res_probes,
-                                   (size_t)n_retire * cfg.nprobe_max * 4, hipMemcpyDeviceToHost, s));
-    }
+    // The merge writes the records of retiring queries straight into this step's pinned host block (the
+    // stores cross the bus while the kernel is still merging other queries): no copy kernel afterwards.
+    // (A copy on a second stream was tried instead; it ran beside the next step's scan and slowed that
+    // by far more than the transfer takes.)
+    TriDevWs W = P->ws;
+    W.res_block = (uint32_t *)R.down_dev;
+    W.res_probes = (uint32_t *)(R.down_dev + P->down_probe_off);
+    HIP_TRY(tri_launch_merge(P->ctx, W, plan_d, n_plan, (cfg.flags & TRI_FLAG_KEEP_PROBES) != 0, min_chunk));
     if (prof) {
         HIP_TRY(hipMemcpyAsync(R.down_host + P->down_step_off, P->ws.step_dev, sizeof(TriStepDev), hipMemcpyDeviceToHost, s));
         HIP_TRY(hipEventRecord(R.ev[6], s));

@@ -145,8 +145,8 @@ struct TriDevWs {
     TriStepDev *step_dev;     // [1]
     float *scores;            // [score_capacity] candidate buffer: per item 2 * npad words of (score bits, position) pairs
     // results of retiring slots, compact, per step
-    uint32_t *res_block;      // [S][1 + 2*kmax]  n, ids[kmax], score bits[kmax]
-    uint32_t *res_probes;     // [S][nprobe_max]
+    uint32_t *res_block;      // [S][1 + 2*kmax]  n, ids[kmax], score bits[kmax]   (pinned host memory of the step
+    uint32_t *res_probes;     // [S][nprobe_max]                                    in flight, as the GPU addresses it)
 };
 
 struct TriLaunchCtx {
