@@ -14,6 +14,24 @@ __global__ void fill_u32_kernel(uint32_t *p, uint32_t v, size_t n)
     if (i < n) p[i] = v;
 }
 
+// The step's upload block (admission records, plan, query rows), pulled from pinned host memory by a
+// kernel of the pool's own stream: it starts the moment the previous kernel ends, where a runtime copy
+// first spends tens of microseconds being set up.  16 bytes per thread and load.
+__global__ void pull_block_kernel(uint4 *__restrict__ dst, const uint4 *__restrict__ src_host, size_t n16)
+{
+    const size_t stride = (size_t)gridDim.x * blockDim.x;
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n16; i += stride) dst[i] = src_host[i];
+}
+
+hipError_t tri_launch_pull_block(hipStream_t s, void *dst_dev, const void *src_host_as_device, size_t bytes)
+{
+    const size_t n16 = (bytes + 15) / 16;          // (both buffers are padded to 256 bytes)
+    if (n16 == 0) return hipSuccess;
+    const unsigned blocks = (unsigned)std::min<size_t>((n16 + 255) / 256, 2048);
+    hipLaunchKernelGGL(pull_block_kernel, dim3(blocks), dim3(256), 0, s, (uint4 *)dst_dev, (const uint4 *)src_host_as_device, n16);
+    return hipGetLastError();
+}
+
 hipError_t tri_launch_fill_u32(hipStream_t s, uint32_t *p, uint32_t v, size_t n)
 {
     if (n == 0) return hipSuccess;

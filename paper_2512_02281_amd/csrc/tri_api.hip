@@ -87,6 +87,7 @@ struct StepRec {
     uint8_t *up_host = nullptr;       // pinned: upload block
     uint8_t *down_host = nullptr;     // pinned: result block, probes, step numbers
     uint8_t *down_dev = nullptr;      // the same memory as the GPU addresses it
+    uint8_t *up_dev = nullptr;        // up_host as the GPU addresses it
     int64_t enqueue_ns = 0;           // when search_step enqueued it
     std::vector<uint32_t> retire;     // ticket index per retire_idx
     uint32_t n_items = 0;
@@ -437,6 +438,7 @@ extern "C" int tri_pool_create(const tri_pool_cfg *cfg, void *dev_ws, size_t dev
         R.up_host = P->pinned + i * per;
         R.down_host = R.up_host + round_up_sz(up, 256);
         e = hipHostGetDevicePointer((void **)&R.down_dev, R.down_host, 0);
+        if (e == hipSuccess) e = hipHostGetDevicePointer((void **)&R.up_dev, R.up_host, 0);
         if (e != hipSuccess) { tri_pool_destroy(P); return fail(TRI_EHIP, "hipHostGetDevicePointer -> %s", hipGetErrorString(e)); }
         e = hipEventCreateWithFlags(&R.done, hipEventDisableTiming);
         for (uint32_t j = 0; j < N_EV && e == hipSuccess; ++j) e = hipEventCreate(&R.ev[j]);
@@ -958,7 +960,7 @@ extern "C" int search_step(tri_pool *P, tri_step_stats *st)
     const size_t up_bytes = desc_bytes + plan_bytes + rows_used;   // rows read from device memory are not uploaded
     hipStream_t s = P->stream;
     const bool prof = (cfg.flags & TRI_FLAG_PROFILE) != 0;
-    HIP_TRY(hipMemcpyAsync(P->ws.upload, R.up_host, up_bytes, hipMemcpyHostToDevice, s));
+    HIP_TRY(tri_launch_pull_block(s, P->ws.upload, R.up_dev, up_bytes));
     const TriNewDesc *desc_d = (const TriNewDesc *)P->ws.upload;
     const TriPlanEntry *plan_d = (const TriPlanEntry *)(P->ws.upload + desc_bytes);
     uint8_t *rows_d = P->ws.upload + desc_bytes + plan_bytes;

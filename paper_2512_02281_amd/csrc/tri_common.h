@@ -156,6 +156,7 @@ struct TriLaunchCtx {
 
 // ---- launchers (each returns hipGetLastError() of its launches) -----------------------------
 hipError_t tri_launch_fill_u32(hipStream_t s, uint32_t *p, uint32_t v, size_t n);
+hipError_t tri_launch_pull_block(hipStream_t s, void *dst_dev, const void *src_host_as_device, size_t bytes);
 hipError_t tri_launch_admit(const TriLaunchCtx &c, const TriDevWs &ws, const TriNewDesc *desc_dev,
                             uint8_t *rows_dev, uint32_t n_new);
 // scores[m][ldc] for m rows (pitch a_pitch_bytes) against n rows of b (pitch row_bytes); the metric
