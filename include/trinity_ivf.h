@@ -50,8 +50,11 @@ typedef enum {
 enum { TRI_L2 = 0, TRI_IP = 1 };          /* metric: squared L2 (smaller = better), inner product (larger = better) */
 enum { TRI_F32 = 0, TRI_F16 = 1 };        /* storage type of an index's vectors and of its queries                  */
 enum { TRI_CLASS_HIGH = 0, TRI_CLASS_LOW = 1 }; /* Sec. 3.3: prefill-side (latency critical) / decode-side requests */
-enum { TRI_FLAG_PROFILE = 1u,             /* bracket every kernel of a step with HIP events (tri_pool_kernel_times)  */
-       TRI_FLAG_KEEP_PROBES = 2u };       /* copy each query's probe list back so search_probes() can return it      */
+enum { TRI_FLAG_PROFILE = 1u,             /* bracket every stage of a step with HIP events (tri_pool_kernel_times);
+                                             the seven events cost about a quarter of a millisecond per step         */
+       TRI_FLAG_KEEP_PROBES = 2u,         /* copy each query's probe list back so search_probes() can return it      */
+       TRI_FLAG_PROFILE_SCAN = 4u };      /* bracket only the list scan (two events): scan_ms and the scan_* counters
+                                             of tri_pool_kernel_times are filled, the other stage times stay zero    */
 
 /* Limits of this implementation (checked, TRI_EINVAL beyond them). */
 #define TRI_KMAX_LIMIT 1024u      /* largest k a pool can be configured for           */
@@ -290,6 +293,9 @@ typedef struct {
     uint64_t scan_items;     /* work items scanned                                                 */
 } tri_kernel_times;
 int tri_pool_kernel_times(tri_pool *pool, tri_kernel_times *out /*[host] out*/, int reset);
+/* Switch the profiling of the steps enqueued from now on: flags = 0, TRI_FLAG_PROFILE or
+ * TRI_FLAG_PROFILE_SCAN (the other flags of the pool are fixed at creation). */
+int tri_pool_set_profiling(tri_pool *pool, uint32_t flags);
 
 const char *tri_last_error(void);
 const char *tri_version(void);

@@ -17,7 +17,7 @@ TRI_OK, TRI_EINVAL, TRI_ENOMEM, TRI_EAGAIN, TRI_EHIP, TRI_ENOENT = 0, -1, -2, -3
 TRI_L2, TRI_IP = 0, 1
 TRI_F32, TRI_F16 = 0, 1
 TRI_CLASS_HIGH, TRI_CLASS_LOW = 0, 1
-TRI_FLAG_PROFILE, TRI_FLAG_KEEP_PROBES = 1, 2
+TRI_FLAG_PROFILE, TRI_FLAG_KEEP_PROBES, TRI_FLAG_PROFILE_SCAN = 1, 2, 4
 TRI_ORDER_FIFO, TRI_ORDER_SLACK = 0, 1
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
@@ -87,7 +87,7 @@ EXPORTS = ["tri_pool_workspace_bytes", "tri_pool_create", "tri_pool_destroy", "i
            "ivf_export", "ivf_info", "ivf_destroy", "search_submit", "search_submit_batch", "search_submit_batch_dev",
            "search_step", "search_poll", "search_poll_batch", "search_probes", "search_cancel", "search_sync",
            "search_run_stream", "search_set_policy", "search_get_policy", "tri_policy_split", "tri_policy_slack_order",
-           "tri_pool_kernel_times", "tri_last_error", "tri_version"]
+           "tri_pool_kernel_times", "tri_pool_set_profiling", "tri_last_error", "tri_version"]
 
 
 def _load():
@@ -123,6 +123,7 @@ def _load():
     lib.tri_policy_split.argtypes = [u32, u32, u32, ctypes.c_float, P(u32), P(u32)]
     lib.tri_policy_slack_order.argtypes = [u32, vp, vp, ctypes.c_int64, ctypes.c_int64, u32, vp]
     lib.tri_pool_kernel_times.argtypes = [vp, P(tri_kernel_times), ctypes.c_int]
+    lib.tri_pool_set_profiling.argtypes = [vp, u32]
     lib.tri_last_error.restype = ctypes.c_char_p
     lib.tri_version.restype = ctypes.c_char_p
     for name in EXPORTS:
@@ -168,6 +169,10 @@ def tri_pool_create(cfg: tri_pool_cfg, dev_ws_ptr: int, dev_ws_bytes: int) -> in
 
 def tri_pool_destroy(pool: int) -> None:
     _check(_lib.tri_pool_destroy(ctypes.c_void_p(pool)), "tri_pool_destroy")
+
+
+def tri_pool_set_profiling(pool: int, flags: int) -> None:
+    _check(_lib.tri_pool_set_profiling(ctypes.c_void_p(pool), flags), "tri_pool_set_profiling")
 
 
 def tri_pool_kernel_times(pool: int, reset: bool = False) -> tri_kernel_times:

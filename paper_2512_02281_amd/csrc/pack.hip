@@ -146,7 +146,8 @@ __global__ __launch_bounds__(1024) void pack_scan_kernel(const uint32_t *__restr
                                                          uint64_t *__restrict__ score_base,
                                                          TriStepDev *__restrict__ step_dev,
                                                          uint32_t *__restrict__ tile_counter, uint32_t min_chunk,
-                                                         uint64_t *__restrict__ block_tot)
+                                                         uint64_t *__restrict__ block_tot,
+                                                         TriStepDev *__restrict__ step_host)
 {
     __shared__ uint32_t s_items[1024], s_tiles[1024], s_lists[1024], s_stiles[1024];
     __shared__ uint64_t s_scores[1024], s_tbytes[1024], s_ubytes[1024];
@@ -243,6 +244,7 @@ __global__ __launch_bounds__(1024) void pack_scan_kernel(const uint32_t *__restr
         step_dev->total_scores = base[4] + s_scores[t];
         step_dev->tile_vec_bytes = base[5] + s_tbytes[t];
         step_dev->unique_vec_bytes = base[6] + s_ubytes[t];
+        if (step_host) *step_host = *step_dev;       // a copy for the host's statistics (pinned host memory)
         for (uint32_t k = 0; k < 2 * TRI_SCAN_CLASSES; ++k) tile_counter[k] = 0;
     }
 }
@@ -331,10 +333,10 @@ hipError_t tri_launch_pack(const TriLaunchCtx &c, const TriDevWs &ws, const TriP
     if (nb > 1)
         hipLaunchKernelGGL(pack_scan_kernel<false>, dim3(nb), dim3(1024), 0, c.stream, ws.hist, n_order, ws.glist_order,
                            ws.list_start, ws.tile_base, ws.stile_base, ws.score_base, ws.step_dev, ws.tile_counter,
-                           min_chunk, ws.pack_tot);
+                           min_chunk, ws.pack_tot, (TriStepDev *)nullptr);
     hipLaunchKernelGGL(pack_scan_kernel<true>, dim3(nb ? nb : 1), dim3(1024), 0, c.stream, ws.hist, n_order, ws.glist_order,
                        ws.list_start, ws.tile_base, ws.stile_base, ws.score_base, ws.step_dev, ws.tile_counter, min_chunk,
-                       ws.pack_tot);
+                       ws.pack_tot, ws.step_host);
     hipLaunchKernelGGL(pack_scatter_kernel, dim3((n_items + 255) / 256), dim3(256), 0, c.stream, n_items,
                        ws.item_glist, ws.item_slot, ws.item_rank, ws.list_start, ws.score_base, ws.glist_len,
                        ws.sorted_slot, ws.item_score_off, ws.item_sorted_pos);

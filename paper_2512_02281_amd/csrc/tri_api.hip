@@ -80,7 +80,8 @@ struct SlotH {
 
 struct StepRec {
     bool in_use = false;
-    bool profiled = false;
+    bool profiled = false;            // all stages bracketed by events
+    bool profiled_scan = false;       // only the list scan bracketed
     uint64_t seq = 0;
     hipEvent_t done = nullptr;
     hipEvent_t ev[N_EV] = {};
@@ -284,9 +285,12 @@ int reap(tri_pool *P, bool block, uint32_t *finished)
             if (P->log_done) P->done_log.push_back(ti);
             ++fin;
         }
-        if (R->profiled) {
+        if (R->profiled || R->profiled_scan) {
             float ms[N_EV - 1] = {};
-            for (uint32_t i = 0; i + 1 < N_EV; ++i) HIP_TRY(hipEventElapsedTime(&ms[i], R->ev[i], R->ev[i + 1]));
+            if (R->profiled)
+                for (uint32_t i = 0; i + 1 < N_EV; ++i) HIP_TRY(hipEventElapsedTime(&ms[i], R->ev[i], R->ev[i + 1]));
+            else if (R->had_scan)
+                HIP_TRY(hipEventElapsedTime(&ms[4], R->ev[4], R->ev[5]));
             const TriStepDev *sd = (const TriStepDev *)(R->down_host + P->down_step_off);
             P->times.steps += 1;
             P->times.admit_ms += ms[0];
@@ -441,7 +445,7 @@ extern "C" int tri_pool_create(const tri_pool_cfg *cfg, void *dev_ws, size_t dev
         if (e == hipSuccess) e = hipHostGetDevicePointer((void **)&R.up_dev, R.up_host, 0);
         if (e != hipSuccess) { tri_pool_destroy(P); return fail(TRI_EHIP, "hipHostGetDevicePointer -> %s", hipGetErrorString(e)); }
         e = hipEventCreateWithFlags(&R.done, hipEventDisableTiming);
-        for (uint32_t j = 0; j < N_EV && e == hipSuccess; ++j) e = hipEventCreate(&R.ev[j]);
+        for (uint32_t j = 0; j < N_EV && e == hipSuccess; ++j) e = hipEventCreateWithFlags(&R.ev[j], hipEventDisableSystemFence);   // (timing only: nothing on the host reads what the kernels between them wrote)
         if (e != hipSuccess) { tri_pool_destroy(P); return fail(TRI_EHIP, "hipEventCreate -> %s", hipGetErrorString(e)); }
     }
     try {
@@ -960,6 +964,7 @@ extern "C" int search_step(tri_pool *P, tri_step_stats *st)
     const size_t up_bytes = desc_bytes + plan_bytes + rows_used;   // rows read from device memory are not uploaded
     hipStream_t s = P->stream;
     const bool prof = (cfg.flags & TRI_FLAG_PROFILE) != 0;
+    const bool prof_scan = !prof && (cfg.flags & TRI_FLAG_PROFILE_SCAN) != 0;
     HIP_TRY(tri_launch_pull_block(s, P->ws.upload, R.up_dev, up_bytes));
     const TriNewDesc *desc_d = (const TriNewDesc *)P->ws.upload;
     const TriPlanEntry *plan_d = (const TriPlanEntry *)(P->ws.upload + desc_bytes);
@@ -986,30 +991,29 @@ extern "C" int search_step(tri_pool *P, tri_step_stats *st)
     if (prof) HIP_TRY(hipEventRecord(R.ev[2], s));
     // chunk length floor of this step: with fewer tiles than a few per wavefront, cut the lists finer
     const uint32_t min_chunk = n_items > 8u * P->ctx.n_cu ? 1024u : 64u;
-    HIP_TRY(tri_launch_pack(P->ctx, P->ws, plan_d, n_plan, n_items, P->total_lists, P->n_order, min_chunk));
+    // Everything the host wants back lands in this step's pinned host block, written by the kernels
+    // themselves (the stores cross the bus while the kernels work on): no copy after the step.
+    // (A result copy on a second stream was tried instead; it ran beside the next step's scan and slowed
+    // that by far more than the transfer takes.)
+    TriDevWs W = P->ws;
+    W.res_block = (uint32_t *)R.down_dev;
+    W.res_probes = (uint32_t *)(R.down_dev + P->down_probe_off);
+    W.step_host = prof || prof_scan ? (TriStepDev *)(R.down_dev + P->down_step_off) : nullptr;
+    HIP_TRY(tri_launch_pack(P->ctx, W, plan_d, n_plan, n_items, P->total_lists, P->n_order, min_chunk));
     if (prof) HIP_TRY(hipEventRecord(R.ev[3], s));
     // thresholds: score a sample of every probed list, k-th best of each slot's sample
     if (n_items) HIP_TRY(tri_launch_scan(P->ctx, P->ws, P->attached_row_bytes, P->scan_class_mask, true));
     if (n_items) HIP_TRY(tri_launch_threshold(P->ctx, P->ws, plan_d, n_plan));
-    if (prof) HIP_TRY(hipEventRecord(R.ev[4], s));
+    if (prof || (prof_scan && n_items)) HIP_TRY(hipEventRecord(R.ev[4], s));
     if (n_items) HIP_TRY(tri_launch_scan(P->ctx, P->ws, P->attached_row_bytes, P->scan_class_mask, false));
-    if (prof) HIP_TRY(hipEventRecord(R.ev[5], s));
-    // The merge writes the records of retiring queries straight into this step's pinned host block (the
-    // stores cross the bus while the kernel is still merging other queries): no copy kernel afterwards.
-    // (A copy on a second stream was tried instead; it ran beside the next step's scan and slowed that
-    // by far more than the transfer takes.)
-    TriDevWs W = P->ws;
-    W.res_block = (uint32_t *)R.down_dev;
-    W.res_probes = (uint32_t *)(R.down_dev + P->down_probe_off);
+    if (prof || (prof_scan && n_items)) HIP_TRY(hipEventRecord(R.ev[5], s));
     HIP_TRY(tri_launch_merge(P->ctx, W, plan_d, n_plan, (cfg.flags & TRI_FLAG_KEEP_PROBES) != 0, min_chunk));
-    if (prof) {
-        HIP_TRY(hipMemcpyAsync(R.down_host + P->down_step_off, P->ws.step_dev, sizeof(TriStepDev), hipMemcpyDeviceToHost, s));
-        HIP_TRY(hipEventRecord(R.ev[6], s));
-    }
+    if (prof) HIP_TRY(hipEventRecord(R.ev[6], s));
     HIP_TRY(hipEventRecord(R.done, s));
     R.in_use = true;
     R.enqueue_ns = now_ns();
     R.profiled = prof;
+    R.profiled_scan = prof_scan;
     R.seq = P->step_seq;
     R.n_items = n_items;
     R.had_scan = n_items != 0;
@@ -1311,6 +1315,15 @@ extern "C" int search_run_stream(tri_pool *P, const tri_query *q, const double *
     }
     if (out) *out = acc;
     return rc;
+}
+
+extern "C" int tri_pool_set_profiling(tri_pool *P, uint32_t flags)
+{
+    if (!P) return fail(TRI_EINVAL, "pool is NULL");
+    if (flags & ~(uint32_t)(TRI_FLAG_PROFILE | TRI_FLAG_PROFILE_SCAN)) return fail(TRI_EINVAL, "only the profiling flags can be changed");
+    std::lock_guard<std::mutex> lk(P->mu);
+    P->cfg.flags = (P->cfg.flags & ~(uint32_t)(TRI_FLAG_PROFILE | TRI_FLAG_PROFILE_SCAN)) | flags;
+    return TRI_OK;
 }
 
 extern "C" int tri_pool_kernel_times(tri_pool *P, tri_kernel_times *out, int reset)

@@ -117,6 +117,7 @@ struct TriDevWs {
     uint32_t *glist_len;      // [max_total_lists]
     uint32_t *glist_voff;     // [max_total_lists] first stored position inside its index
     uint32_t *glist_index;    // [max_total_lists]
+    TriStepDev *step_host;    // NULL, or where the step totals are mirrored for the host (pinned host memory)
     uint64_t *pack_tot;       // [16][8] per-span totals of the pack prefix sums
     uint4 *glist_order;       // [max_total_lists] attached lists by descending byte length (scan order):
                               //   {pool-wide list number, length, row bytes, 0}
