@@ -989,8 +989,12 @@ extern "C" int search_step(tri_pool *P, tri_step_stats *st)
         a = b;
     }
     if (prof) HIP_TRY(hipEventRecord(R.ev[2], s));
-    // chunk length floor of this step: with fewer tiles than a few per wavefront, cut the lists finer
-    const uint32_t min_chunk = n_items > 8u * P->ctx.n_cu ? 1024u : 64u;
+    // chunk length floor of this step: with fewer tiles than a few per wavefront, cut the lists finer.
+    // Tiles are estimated from the item count: below one item per attached list every item is a tile of
+    // its own, above it a list's items share tiles of TRI_QT queries.
+    const uint64_t per_list = P->n_order ? (n_items + P->n_order - 1) / P->n_order : 1;
+    const uint64_t tiles_est = n_items <= P->n_order ? n_items : (uint64_t)P->n_order * ((per_list + TRI_QT - 1) / TRI_QT);
+    const uint32_t min_chunk = tiles_est < 16u * P->ctx.n_cu ? 128u : 1024u;
     // Everything the host wants back lands in this step's pinned host block, written by the kernels
     // themselves (the stores cross the bus while the kernels work on): no copy after the step.
     // (A result copy on a second stream was tried instead; it ran beside the next step's scan and slowed
