@@ -172,7 +172,8 @@ __global__ __launch_bounds__(1024) void pack_scan_kernel(const uint32_t *__restr
             if (c) {
                 const uint32_t len = o[u].y;
                 const uint32_t nt = (c + TRI_QT - 1) / TRI_QT;
-                const uint64_t bytes = (uint64_t)len * o[u].z;
+                // (bytes the MAIN scan launch has to read: the list without its first block, which the sample launch scores)
+                const uint64_t bytes = (uint64_t)(len > TRI_SAMPLE_VECS ? len - TRI_SAMPLE_VECS : 0u) * o[u].z;
                 items += c;
                 tiles += nt * ((len + tri_chunk_vecs(len, min_chunk) - 1) / tri_chunk_vecs(len, min_chunk));
                 stiles += len ? nt : 0;

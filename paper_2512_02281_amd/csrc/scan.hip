@@ -197,8 +197,11 @@ __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(1, 1))) void
             // (sized to whole blocks: a 16-byte load never straddles its end; the norm array has a block of slack)
             const __amdgpu_buffer_rsrc_t nrs =
                 __builtin_amdgcn_make_buffer_rsrc((void *)tl.vnorm_addr, 0, nblocks * TRI_VB * 4u, SCAN_BUF_FLAGS);
+            // (main launch: the first block of a list was scored by the sample launch, and what passed of it
+            // already heads the candidate regions; the scan of a list's first chunk starts at its second block)
+            const uint32_t b0 = FILTER && tl.vec_begin == 0 ? 1u : 0u;
             // the stream's first RG groups go out before anything else
-            uint32_t off = r * row_bytes + kg * 16;
+            uint32_t off = r * row_bytes + kg * 16 + b0 * blk_bytes;
             uint4 buf[RG][4];
 #pragma unroll
             for (int g = 0; g < RG; ++g) {
@@ -228,6 +231,7 @@ __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(1, 1))) void
             const float qn_own = live ? slot_qnorm[slot] : 0.f;
             const bool l2_own = live ? slot_meta[slot].metric == 0u : false;
             const uint32_t thr_own = FILTER && live ? thr_key[slot] : 0u;
+            const uint32_t cnt_own = b0 && live ? surv_count[(tl.item_pos + r) * TRI_TILES_PER_ITEM] : 0u;
             const uint32_t l2_all = (uint32_t)__ballot(l2_own && lane < 32);
             float qn[16];
             uint32_t thr[16];
@@ -240,7 +244,7 @@ __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(1, 1))) void
                 l2mask |= ((l2_all >> j) & 1u) << i;
             }
             uint32_t stage_n = 0;
-            if constexpr (FILTER) qcnt[r] = 0u;
+            if constexpr (FILTER) qcnt[r] = cnt_own;
             const uint32_t pitch_bytes = tl.pitch * 4u;
             // output region of the tile: dense rows of nblocks*32 scores, or (query, chunk) pair regions
             const __amdgpu_buffer_rsrc_t ors = __builtin_amdgcn_make_buffer_rsrc(
@@ -249,7 +253,7 @@ __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(1, 1))) void
             const uint32_t lane_off = 4 * kg * pitch_bytes + r * 4;
             __builtin_amdgcn_sched_barrier(0);
 
-            for (uint32_t b = 0; b < nblocks; ++b, off += blk_bytes) {
+            for (uint32_t b = b0; b < nblocks; ++b, off += blk_bytes) {
                 // |x|^2 of this lane's vector, issued before the prefetches below so that waiting
                 // for it never waits for them (vector-memory operations complete in order)
                 const float vn = __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(nrs, (b * TRI_VB + r) * 4u, 0, 0));
@@ -333,7 +337,8 @@ __device__ __forceinline__ void scan_tile_pipelined(const TriTile &tl, const uin
     const uint32_t lane_off = 4 * kg * pitch_bytes + r * 4;
     constexpr uint32_t bstride = (TRI_SCAN_THREADS / 64) * TRI_VB * row_bytes;   // to the wavefront's next block
 
-    uint32_t off = (wave * TRI_VB + r) * row_bytes + kg * 16;
+    const uint32_t b0 = FILTER && tl.vec_begin == 0 ? 1u : 0u;    // (the sample launch scored the list's first block)
+    uint32_t off = ((b0 + wave) * TRI_VB + r) * row_bytes + kg * 16;
     uint4 buf[SCAN_RING][4];
 #pragma unroll
     for (int s = 0; s < SCAN_RING; ++s) {
@@ -341,7 +346,7 @@ __device__ __forceinline__ void scan_tile_pipelined(const TriTile &tl, const uin
         for (int c = 0; c < 4; ++c) buf[s][c] = scan_ld16(vrs, off + s * 128 + c * 32);
         __builtin_amdgcn_sched_barrier(0);
     }
-    for (uint32_t b = wave; b < nblocks; b += TRI_SCAN_THREADS / 64, off += bstride) {
+    for (uint32_t b = b0 + wave; b < nblocks; b += TRI_SCAN_THREADS / 64, off += bstride) {
         const float vn = __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(nrs, (b * TRI_VB + r) * 4u, 0, 0));
         __builtin_amdgcn_sched_barrier(0);
         tri_f32x16 acc;
@@ -402,7 +407,8 @@ __device__ __forceinline__ void scan_tile_generic(const TriTile &tl, const uint8
         SCAN_BUF_FLAGS);
     const uint32_t lane_off = 4 * kg * pitch_bytes + r * 4;
 
-    for (uint32_t b = wave; b < nblocks; b += TRI_SCAN_THREADS / 64) {
+    const uint32_t b0 = FILTER && tl.vec_begin == 0 ? 1u : 0u;    // (the sample launch scored the list's first block)
+    for (uint32_t b = b0 + wave; b < nblocks; b += TRI_SCAN_THREADS / 64) {
         const uint32_t off = (b * TRI_VB + r) * row_bytes + kg * 16;
         const float vn = __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(nrs, (b * TRI_VB + r) * 4u, 0, 0));
         tri_f32x16 acc;
@@ -460,7 +466,8 @@ __global__ __launch_bounds__(TRI_SCAN_THREADS) __attribute__((amdgpu_waves_per_e
             sh.qnorm[j] = slot != 0xFFFFFFFFu ? slot_qnorm[slot] : 0.f;
             sh.metric[j] = slot != 0xFFFFFFFFu ? slot_meta[slot].metric : 1u;
             sh.thr[j] = FILTER && slot != 0xFFFFFFFFu ? thr_key[slot] : 0u;
-            sh.cnt[j] = 0u;
+            // (a list's first chunk counts on from the sample's candidates)
+            sh.cnt[j] = FILTER && tl.vec_begin == 0 && j < tl.nq ? surv_count[(tl.item_pos + j) * TRI_TILES_PER_ITEM] : 0u;
         }
         __syncthreads();
         // stage the tile's query rows; rows past nq are zero (masked padding)

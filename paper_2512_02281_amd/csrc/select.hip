@@ -627,8 +627,10 @@ __global__ __launch_bounds__(TRI_SEL_THREADS) void slot_threshold_kernel(
     const uint32_t *__restrict__ item_glist, const uint32_t *__restrict__ item_sorted_pos,
     const uint32_t *__restrict__ glist_len, const float *__restrict__ sample_scores,
     const float *__restrict__ topk_score, const uint32_t *__restrict__ topk_count, uint32_t kmax,
-    uint32_t *__restrict__ thr_key)
+    uint32_t *__restrict__ thr_key, const uint64_t *__restrict__ item_score_off, float *__restrict__ cand,
+    uint32_t *__restrict__ surv_count)
 {
+    static_assert(TRI_SAMPLE_VECS == TRI_VB && TRI_SAMPLE_VECS == 32, "the sample is the first block of a list");
     __shared__ SelShared sh;
     const TriPlanEntry e = plan[blockIdx.x];
     const TriSlotMeta meta = slot_meta[e.slot];
@@ -636,13 +638,14 @@ __global__ __launch_bounds__(TRI_SEL_THREADS) void slot_threshold_kernel(
     const uint32_t have = e.cursor > 0 ? topk_count[e.slot] : 0u;
     const uint32_t nitems = e.take < TRI_THRESH_ITEMS ? e.take : TRI_THRESH_ITEMS;
     uint32_t *keys = (uint32_t *)sh.pool;                  // room for 2 * SEL_CAP keys
-    // per item: where its sample row is and how many of its TRI_SAMPLE_VECS scores exist
-    uint32_t *row_of = sh.hist, *len_of = sh.hist + TRI_THRESH_ITEMS;
+    // per item (kept in the segment cache, which this kernel does not use otherwise): .off = its sample
+    // row, .len = how many of its TRI_SAMPLE_VECS scores exist, .id_off = first pair of its candidate region
+    const uint32_t ncached = e.take < SEL_SEGCACHE ? e.take : SEL_SEGCACHE;
     if (threadIdx.x == 0) sh.cnt = 0;
-    for (uint32_t s = threadIdx.x; s < nitems; s += TRI_SEL_THREADS) {
+    for (uint32_t s = threadIdx.x; s < ncached; s += TRI_SEL_THREADS) {
         const uint32_t it = e.item_base + s;
-        row_of[s] = item_sorted_pos[it];
-        len_of[s] = min(glist_len[item_glist[it]], (uint32_t)TRI_SAMPLE_VECS);
+        sh.seg[s] = SelSeg{item_sorted_pos[it], min(glist_len[item_glist[it]], (uint32_t)TRI_SAMPLE_VECS),
+                           (uint32_t)(item_score_off[it] / 2u), 0u};
     }
     __syncthreads();
     // keys[s * 32 + l] = key of sample l of item s (all-ones where the list is shorter), then the running top-k
@@ -652,7 +655,7 @@ __global__ __launch_bounds__(TRI_SEL_THREADS) void slot_threshold_kernel(
         uint32_t key = 0xFFFFFFFFu;
         if (i < nsample) {
             const uint32_t s = i / TRI_SAMPLE_VECS, l = i % TRI_SAMPLE_VECS;
-            if (l < len_of[s]) key = sel_key(sample_scores[(size_t)row_of[s] * TRI_SAMPLE_VECS + l], desc);
+            if (l < sh.seg[s].len) key = sel_key(sample_scores[(size_t)sh.seg[s].off * TRI_SAMPLE_VECS + l], desc);
         } else {
             key = sel_key(topk_score[(size_t)e.slot * kmax + (i - nsample)], desc);
         }
@@ -666,6 +669,31 @@ __global__ __launch_bounds__(TRI_SEL_THREADS) void slot_threshold_kernel(
     uint32_t thr = 0xFFFFFFFFu;
     if (nvalid >= meta.k) thr = sel_keys_threshold(sh, keys, n, meta.k);
     if (threadIdx.x == 0) thr_key[e.slot] = thr;
+    // The sample IS the first block of every list: its scores that pass the threshold become the first
+    // candidates of their (query, list) item here, and the scan starts at the second block.  One item per
+    // half-wavefront; (score bits, position) pairs at the head of the item's region, their number in the
+    // item's first counter (the scan counts on from there).
+    // (The first TRI_THRESH_ITEMS items' keys are still in LDS -- a key gives back its score bit for bit --;
+    // items beyond them, and beyond the cached descriptors, are read again.)
+    const uint32_t l = threadIdx.x & 31;
+    for (uint32_t s = threadIdx.x >> 5; s < e.take; s += TRI_SEL_THREADS / 32) {
+        uint32_t row, n_l, first_pair;
+        if (s < ncached) {
+            row = sh.seg[s].off; n_l = sh.seg[s].len; first_pair = sh.seg[s].id_off;
+        } else {
+            const uint32_t it = e.item_base + s;
+            row = item_sorted_pos[it];
+            n_l = min(glist_len[item_glist[it]], (uint32_t)TRI_SAMPLE_VECS);
+            first_pair = (uint32_t)(item_score_off[it] / 2u);
+        }
+        uint32_t key = 0xFFFFFFFFu;
+        if (l < n_l) key = s < nitems ? keys[s * TRI_SAMPLE_VECS + l] : sel_key(sample_scores[(size_t)row * TRI_SAMPLE_VECS + l], desc);
+        const bool pass = l < n_l && key <= thr;
+        const uint64_t m = __ballot(pass);
+        const uint32_t half = (threadIdx.x & 32) ? (uint32_t)(m >> 32) : (uint32_t)m;
+        if (pass) ((uint2 *)cand)[(size_t)first_pair + __popc(half & ((1u << l) - 1u))] = make_uint2(__float_as_uint(sel_unkey(key, desc)), l);
+        if (l == 0) surv_count[row * TRI_TILES_PER_ITEM] = (uint32_t)__popc(half);
+    }
 }
 
 hipError_t tri_launch_threshold(const TriLaunchCtx &c, const TriDevWs &ws, const TriPlanEntry *plan_dev, uint32_t n_plan)
@@ -673,7 +701,7 @@ hipError_t tri_launch_threshold(const TriLaunchCtx &c, const TriDevWs &ws, const
     if (n_plan == 0) return hipSuccess;
     hipLaunchKernelGGL(slot_threshold_kernel, dim3(n_plan), dim3(TRI_SEL_THREADS), 0, c.stream, plan_dev, ws.slot_meta,
                        ws.item_glist, ws.item_sorted_pos, ws.glist_len, ws.sample_scores, ws.topk_score, ws.topk_count,
-                       c.kmax, ws.thr_key);
+                       c.kmax, ws.thr_key, ws.item_score_off, ws.scores, ws.surv_count);
     return hipGetLastError();
 }
 
