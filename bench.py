@@ -301,6 +301,8 @@ def stream_bench(args, tri, workloads, torch):
              "mean_running_slots": round(st.running / max(st.steps, 1), 1), "longest_queue": int(st.max_pending),
              "latency_ms_p50_p99": {"all": pct(lat), "rag_low_class": pct(lat[is_rag]), "cache_high_class": pct(lat[~is_rag])},
              "cache_hit_rate": round(float((dist[~is_rag, 0] >= 0.95).mean()), 4),
+             "host_s": {"wall": round(st.wall_s, 4), "submit": round(st.submit_s, 4), "search_step": round(st.step_s, 4),
+                        "collect": round(st.collect_s, 4)},
              "scan_ms_per_step": round(kt.scan_ms / max(kt.scan_launches, 1), 4),
              "scan_unique_GBs": round(kt.scan_unique_bytes / max(kt.scan_ms, 1e-9) / 1e6, 1)}
         log(str(r))

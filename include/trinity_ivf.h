@@ -270,6 +270,10 @@ typedef struct {
     uint64_t capacity;     /* W summed over those steps: 1 - items / capacity is the padding share   */
     uint64_t running;      /* occupied slots summed over those steps                                */
     uint64_t max_pending;  /* longest the two queues together ever were                             */
+    double submit_s;       /* host time spent queueing arrivals (copies of the query vectors)        */
+    double step_s;         /* host time spent inside search_step (planning, enqueueing; includes waiting
+                              for the oldest step when `depth` are in flight)                       */
+    double collect_s;      /* host time spent collecting finished results                           */
 } tri_stream_stats;
 int search_run_stream(tri_pool *pool, const tri_query *q /*[host] n*/, const double *arrival_s /*[host] n*/, uint32_t n,
                       uint32_t depth, uint32_t stride, uint32_t *n_out /*[host] n*/, int64_t *ids /*[host] n*stride*/,

@@ -80,7 +80,8 @@ class tri_policy(ctypes.Structure):
 
 class tri_stream_stats(ctypes.Structure):
     _fields_ = [("wall_s", ctypes.c_double), ("steps", ctypes.c_uint64), ("items", ctypes.c_uint64),
-                ("capacity", ctypes.c_uint64), ("running", ctypes.c_uint64), ("max_pending", ctypes.c_uint64)]
+                ("capacity", ctypes.c_uint64), ("running", ctypes.c_uint64), ("max_pending", ctypes.c_uint64),
+                ("submit_s", ctypes.c_double), ("step_s", ctypes.c_double), ("collect_s", ctypes.c_double)]
 
 
 EXPORTS = ["tri_pool_workspace_bytes", "tri_pool_create", "tri_pool_destroy", "ivf_build_bytes", "ivf_build",

@@ -78,6 +78,17 @@ struct SlotH {
     tri_index *index = nullptr;
 };
 
+// Where search_run_stream wants finished results delivered: straight from a step's pinned block into the
+// caller's arrays (row = the query's position in the stream), without the stop in the ticket store.
+struct StreamSink {
+    const uint32_t *q_of_ticket;
+    uint32_t *n_out;
+    int64_t *ids;
+    float *dist;
+    uint32_t *probes;
+    uint32_t stride;
+};
+
 struct StepRec {
     bool in_use = false;
     bool profiled = false;            // all stages bracketed by events
@@ -129,7 +140,8 @@ struct tri_pool {
     // tickets
     std::vector<Ticket> tickets;
     std::vector<uint32_t> free_tickets;
-    std::vector<uint8_t> qstore;       // [max_outstanding][max_row_bytes] padded query rows
+    uint8_t *qstore = nullptr;         // pinned [max_outstanding][max_row_bytes]: padded rows of host-submitted queries,
+    uint8_t *qstore_dev = nullptr;     //   read by the admitting step's kernel straight from there (same memory, GPU address)
     std::vector<uint32_t> res_ids;     // [max_outstanding][kmax]
     std::vector<float> res_score;      // [max_outstanding][kmax]
     std::vector<uint32_t> res_probe;   // [max_outstanding][nprobe_max] (only with KEEP_PROBES)
@@ -144,13 +156,15 @@ struct tri_pool {
     tri_kernel_times times{};
     // scratch vectors reused by search_step
     std::vector<uint32_t> order, newq;
+    std::vector<uint32_t> run_order[2];   // running slots per class, in admission order (with the admission number
+    std::vector<uint64_t> run_seq[2];     //   each had then: a slot number alone could be a later occupant)
     // scheduling policy (Sec. 3.3) and the measured mean step duration its slack order uses
     tri_policy policy{1.0f, TRI_ORDER_FIFO, 0.0, 0.0};
     double mean_step_s = 0.0;
     int64_t last_done_ns = 0;
     // search_run_stream: tickets in the order their results arrived
-    bool log_done = false;
     std::vector<uint32_t> done_log;
+    const StreamSink *sink = nullptr;
 };
 
 namespace {
@@ -277,12 +291,29 @@ int reap(tri_pool *P, bool block, uint32_t *finished)
             }
             const uint32_t *rec = blk + i * (1 + 2 * (size_t)kmax);
             t.n_out = rec[0];
+            if (P->sink) {
+                const StreamSink &K = *P->sink;
+                const uint32_t qi = K.q_of_ticket[ti];
+                int64_t *oi = K.ids + (size_t)qi * K.stride;
+                float *od = K.dist + (size_t)qi * K.stride;
+                const float *sc = (const float *)(rec + 1 + kmax);
+                for (uint32_t j = 0; j < t.n_out; ++j) { oi[j] = (int64_t)rec[1 + j]; od[j] = sc[j]; }
+                const float pad = t.metric == TRI_L2 ? __builtin_inff() : -__builtin_inff();
+                for (uint32_t j = t.n_out; j < t.k; ++j) { oi[j] = -1; od[j] = pad; }
+                K.n_out[qi] = t.n_out;
+                if (K.probes) memcpy(K.probes + (size_t)qi * pmax, prb + i * (size_t)pmax, (size_t)t.nprobe * 4);
+                P->done_log.push_back(qi);
+                t.state = T_FREE;
+                ++t.gen;
+                P->free_tickets.push_back(ti);
+                ++fin;
+                continue;
+            }
             memcpy(&P->res_ids[(size_t)ti * kmax], rec + 1, (size_t)t.n_out * 4);
             memcpy(&P->res_score[(size_t)ti * kmax], rec + 1 + kmax, (size_t)t.n_out * 4);
             if (P->cfg.flags & TRI_FLAG_KEEP_PROBES)
                 memcpy(&P->res_probe[(size_t)ti * pmax], prb + i * (size_t)pmax, (size_t)t.nprobe * 4);
             t.state = T_DONE;
-            if (P->log_done) P->done_log.push_back(ti);
             ++fin;
         }
         if (R->profiled || R->profiled_scan) {
@@ -378,8 +409,8 @@ void enqueue_locked(tri_pool *P, const tri_query *q, tri_ticket *out)
     t.tag = q->user_tag;
     t.submit_ns = now_ns();
     t.deadline_ns = q->deadline_ns ? t.submit_ns + (int64_t)std::min<uint64_t>(q->deadline_ns, (uint64_t)INT64_MAX / 2) : INT64_MAX;
-    t.dev_vec = nullptr;
-    uint8_t *row = &P->qstore[(size_t)ti * P->max_row_bytes];
+    t.dev_vec = P->qstore_dev + (size_t)ti * P->max_row_bytes;   // (set before the copy below; read only after admission)
+    uint8_t *row = P->qstore + (size_t)ti * P->max_row_bytes;
     const uint32_t es = esize(t.index->p.dtype);
     memcpy(row, q->vec, (size_t)t.index->p.dim * es);
     memset(row + (size_t)t.index->p.dim * es, 0, t.index->row_bytes - (size_t)t.index->p.dim * es);
@@ -437,6 +468,9 @@ extern "C" int tri_pool_create(const tri_pool_cfg *cfg, void *dev_ws, size_t dev
     const size_t per = round_up_sz(up, 256) + P->down_bytes;
     e = hipHostMalloc((void **)&P->pinned, per * RING, hipHostMallocDefault);
     if (e != hipSuccess) { delete P; return fail(TRI_EHIP, "hipHostMalloc(%zu) -> %s", per * RING, hipGetErrorString(e)); }
+    e = hipHostMalloc((void **)&P->qstore, (size_t)cfg->max_outstanding * mrb, hipHostMallocDefault);
+    if (e == hipSuccess) e = hipHostGetDevicePointer((void **)&P->qstore_dev, P->qstore, 0);
+    if (e != hipSuccess) { tri_pool_destroy(P); return fail(TRI_EHIP, "hipHostMalloc(query store) -> %s", hipGetErrorString(e)); }
     for (uint32_t i = 0; i < RING; ++i) {
         StepRec &R = P->ring[i];
         R.up_host = P->pinned + i * per;
@@ -452,7 +486,6 @@ extern "C" int tri_pool_create(const tri_pool_cfg *cfg, void *dev_ws, size_t dev
         P->tickets.resize(cfg->max_outstanding);
         P->free_tickets.reserve(cfg->max_outstanding);
         for (uint32_t i = cfg->max_outstanding; i-- > 0;) P->free_tickets.push_back(i);
-        P->qstore.resize((size_t)cfg->max_outstanding * mrb);
         P->res_ids.resize((size_t)cfg->max_outstanding * cfg->kmax);
         P->res_score.resize((size_t)cfg->max_outstanding * cfg->kmax);
         if (cfg->flags & TRI_FLAG_KEEP_PROBES) P->res_probe.resize((size_t)cfg->max_outstanding * cfg->nprobe_max);
@@ -482,6 +515,7 @@ extern "C" int tri_pool_destroy(tri_pool *P)
             if (P->ring[i].ev[j]) (void)hipEventDestroy(P->ring[i].ev[j]);
     }
     if (P->pinned) (void)hipHostFree(P->pinned);
+    if (P->qstore) (void)hipHostFree(P->qstore);
     delete P;
     return TRI_OK;
 }
@@ -857,7 +891,6 @@ extern "C" int search_step(tri_pool *P, tri_step_stats *st)
         if (rc) return rc;
     }
     const tri_pool_cfg &cfg = P->cfg;
-    const uint32_t S = cfg.slots;
     TriNewDesc *desc_h = (TriNewDesc *)R.up_host;
 
     // ---- admit (Sec. 3.3): the free slots are split between the classes by the reserved share, the
@@ -894,6 +927,8 @@ extern "C" int search_step(tri_pool *P, tri_step_stats *st)
                 t.slot = slot;
                 SlotH &sl = P->slots[slot];
                 sl = SlotH{true, ti, t.nprobe, 0u, t.klass, P->admit_seq++, t.index};
+                P->run_order[t.klass].push_back(slot);
+                P->run_seq[t.klass].push_back(sl.admit_seq);
                 ++P->n_running;
                 P->newq.push_back(ti);
             }
@@ -907,14 +942,23 @@ extern "C" int search_step(tri_pool *P, tri_step_stats *st)
     const size_t desc_bytes = round_up_sz((size_t)n_new * sizeof(TriNewDesc), 256);
 
     // ---- plan: every running slot, higher class first, then admission order
+    // (the running slots of each class are kept in admission order; retired ones are dropped here)
     P->order.clear();
-    for (uint32_t s = 0; s < S; ++s)
-        if (P->slots[s].active) P->order.push_back(s);
-    std::sort(P->order.begin(), P->order.end(), [&](uint32_t a, uint32_t b) {
-        const SlotH &x = P->slots[a], &y = P->slots[b];
-        if (x.klass != y.klass) return x.klass < y.klass;
-        return x.admit_seq < y.admit_seq;
-    });
+    for (int klass = 0; klass < 2; ++klass) {
+        std::vector<uint32_t> &ro = P->run_order[klass];
+        size_t w = 0;
+        for (size_t i = 0; i < ro.size(); ++i) {
+            const SlotH &sl = P->slots[ro[i] & 0xFFFFFFFFu];
+            if (sl.active && sl.admit_seq == P->run_seq[klass][i]) {
+                ro[w] = ro[i];
+                P->run_seq[klass][w] = P->run_seq[klass][i];
+                ++w;
+                P->order.push_back(ro[i]);
+            }
+        }
+        ro.resize(w);
+        P->run_seq[klass].resize(w);
+    }
     TriPlanEntry *plan_h = (TriPlanEntry *)(R.up_host + desc_bytes);
     uint32_t n_plan = 0, n_items = 0, n_retire = 0;
     uint64_t score_used = 0;
@@ -950,18 +994,13 @@ extern "C" int search_step(tri_pool *P, tri_step_stats *st)
 
     // ---- upload block: [descs][plan][rows]
     const size_t plan_bytes = round_up_sz((size_t)n_plan * sizeof(TriPlanEntry), 256);
-    uint8_t *rows_h = R.up_host + desc_bytes + plan_bytes;
-    uint32_t row_off = 0, rows_used = 0;
+    uint32_t row_off = 0;
     for (uint32_t i = 0; i < n_new; ++i) {
         const Ticket &t = P->tickets[P->newq[i]];
         desc_h[i] = TriNewDesc{t.slot, t.index->id, t.metric, t.k, t.nprobe, row_off, (uint64_t)(uintptr_t)t.dev_vec};
-        if (!t.dev_vec) {
-            memcpy(rows_h + row_off, &P->qstore[(size_t)P->newq[i] * P->max_row_bytes], t.index->row_bytes);
-            rows_used = row_off + t.index->row_bytes;
-        }
-        row_off += t.index->row_bytes;
+        row_off += t.index->row_bytes;     // (its place in the device row area; the kernel fetches the vector itself)
     }
-    const size_t up_bytes = desc_bytes + plan_bytes + rows_used;   // rows read from device memory are not uploaded
+    const size_t up_bytes = desc_bytes + plan_bytes;   // (query rows are read by the admit kernel from where they lie)
     hipStream_t s = P->stream;
     const bool prof = (cfg.flags & TRI_FLAG_PROFILE) != 0;
     const bool prof_scan = !prof && (cfg.flags & TRI_FLAG_PROFILE_SCAN) != 0;
@@ -1230,12 +1269,16 @@ extern "C" int search_run_stream(tri_pool *P, const tri_query *q, const double *
             if (q[i].k > stride) return fail(TRI_EINVAL, "query %u: k=%u exceeds the row stride %u", i, q[i].k, stride);
             if (i && arrival_s[i] < arrival_s[i - 1]) return fail(TRI_EINVAL, "arrival times must not decrease");
         }
-        P->log_done = true;
         P->done_log.clear();
     }
     if (depth == 0) depth = 2;
     if (depth > RING) depth = RING;
     std::vector<uint32_t> q_of_ticket(P->tickets.size());
+    const StreamSink sink{q_of_ticket.data(), n_out, ids, dist, probes, stride};
+    {
+        std::lock_guard<std::mutex> lk(P->mu);
+        P->sink = &sink;
+    }
     tri_stream_stats acc{};
     using clk = std::chrono::steady_clock;
     const clk::time_point t0 = clk::now();
@@ -1248,6 +1291,7 @@ extern "C" int search_run_stream(tri_pool *P, const tri_query *q, const double *
         {
             std::lock_guard<std::mutex> lk(P->mu);
             const double now = elapsed();
+            const double t_sub = now;
             // (a burst is taken in in portions, so that the first step does not wait for the last copy)
             uint32_t portion = 2 * P->cfg.slots;
             while (next < n && arrival_s[next] <= now && !P->free_tickets.empty() && portion--) {
@@ -1256,24 +1300,17 @@ extern "C" int search_run_stream(tri_pool *P, const tri_query *q, const double *
                 q_of_ticket[(uint32_t)(tk & 0xFFFFFFFFull)] = next;
                 ++next;
             }
+            const double t_col = elapsed();
+            acc.submit_s += t_col - t_sub;
             rc = hipSetDevice(P->device) == hipSuccess ? reap(P, false, nullptr) : fail(TRI_EHIP, "hipSetDevice failed");
             if (rc) break;
-            if (!P->done_log.empty()) {
+            if (!P->done_log.empty()) {              // (reap delivered them into the caller's arrays; here: their time)
                 const double t = elapsed();
-                for (uint32_t ti : P->done_log) {
-                    const uint32_t qi = q_of_ticket[ti];
-                    const tri_ticket tk = ((uint64_t)P->tickets[ti].gen << 32) | ti;
-                    if (probes)
-                        memcpy(probes + (size_t)qi * P->cfg.nprobe_max, &P->res_probe[(size_t)ti * P->cfg.nprobe_max],
-                               (size_t)P->tickets[ti].nprobe * 4);
-                    rc = poll_locked(P, tk, &n_out[qi], ids + (size_t)qi * stride, dist + (size_t)qi * stride, stride);
-                    if (rc) break;
-                    done_s[qi] = t;
-                    ++done;
-                }
+                for (uint32_t qi : P->done_log) done_s[qi] = t;
+                done += (uint32_t)P->done_log.size();
                 P->done_log.clear();
-                if (rc) break;
             }
+            acc.collect_s += elapsed() - t_col;
             for (uint32_t i = 0; i < RING; ++i) inflight += P->ring[i].in_use;
             const uint64_t waiting = P->pending[0].size() + P->pending[1].size();
             have_work = P->n_running > 0 || waiting > 0;
@@ -1295,7 +1332,9 @@ extern "C" int search_run_stream(tri_pool *P, const tri_query *q, const double *
         }
         if (have_work && inflight < depth) {
             tri_step_stats st;
+            const double t_step = elapsed();
             rc = search_step(P, &st);
+            acc.step_s += elapsed() - t_step;
             if (rc) break;
             if (st.items) {
                 acc.steps += 1;
@@ -1314,7 +1353,7 @@ extern "C" int search_run_stream(tri_pool *P, const tri_query *q, const double *
     acc.wall_s = elapsed();
     {
         std::lock_guard<std::mutex> lk(P->mu);
-        P->log_done = false;
+        P->sink = nullptr;
         P->done_log.clear();
     }
     if (out) *out = acc;
