@@ -14,7 +14,7 @@ __global__ void fill_u32_kernel(uint32_t *p, uint32_t v, size_t n)
     if (i < n) p[i] = v;
 }
 
-// The step's upload block (admission records, plan, query rows), pulled from pinned host memory by a
+// The step's upload block (admission records, plan), pulled from pinned host memory by a
 // kernel of the pool's own stream: it starts the moment the previous kernel ends, where a runtime copy
 // first spends tens of microseconds being set up.  16 bytes per thread and load.
 __global__ void pull_block_kernel(uint4 *__restrict__ dst, const uint4 *__restrict__ src_host, size_t n16)
@@ -40,9 +40,9 @@ hipError_t tri_launch_fill_u32(hipStream_t s, uint32_t *p, uint32_t v, size_t n)
 }
 
 // ---------------------------------------------------------------------------------------- admit
-// One workgroup per admitted query: bring its zero-padded row into the slot (from the uploaded row
-// area, or from the caller's device vector, which is then also written to the row area for the
-// coarse contraction), compute |q|^2 in fp32 (fixed order: thread-strided partial sums, then a
+// One workgroup per admitted query: bring its zero-padded row into the slot -- from the pool's pinned
+// query store (host-submitted queries) or from the caller's device vector; either is also written to
+// the step's row area for the coarse contraction --, compute |q|^2 in fp32 (fixed order: thread-strided partial sums, then a
 // tree), write the slot's static description.
 template <typename T>
 __device__ __forceinline__ float admit_row(const TriNewDesc &d, uint32_t dim, uint32_t dpad, uint8_t *rows,
@@ -53,13 +53,8 @@ __device__ __forceinline__ float admit_row(const TriNewDesc &d, uint32_t dim, ui
     const T *dev = (const T *)d.src_dev;
     float part = 0.f;
     for (uint32_t e = threadIdx.x; e < dpad; e += 256) {
-        T v;
-        if (dev) {
-            v = e < dim ? dev[e] : (T)0;
-            up[e] = v;
-        } else {
-            v = up[e];
-        }
+        const T v = e < dim ? dev[e] : (T)0;
+        up[e] = v;
         dst[e] = v;
         const float f = (float)v;
         part += f * f;

@@ -18,19 +18,20 @@
 //    scores written densely; a small kernel then sets each query's threshold to the k-th best of
 //    its sample (and running top-k).  A k-th best of a SUBSET of the candidates can only be worse
 //    than the k-th best of all of them, so nothing that belongs to the top-k is beyond it.
-//  * main launch (FILTER = true): every vector is scored, and only the scores not worse than the
-//    query's threshold are appended, as (score bits, position in list) pairs, to the (query, chunk)
-//    region of the candidate buffer.  The result is exact; the threshold only decides how much is
-//    written (about k / sample size of the scores).
+//  * main launch (FILTER = true): every other vector is scored (the sample was the first block of
+//    each list; what passed of it already heads the candidate regions, put there by the threshold
+//    kernel), and only the scores not worse than the query's threshold are appended, as (score bits,
+//    position in list) pairs, to the (query, chunk) region of the candidate buffer.  The result is
+//    exact; the threshold only decides how much is written (about k / sample size of the scores).
 //
 // Two kernels:
-//  * scan_wave_kernel (rows of 512 / 1024 / 1536 bytes): ONE WAVEFRONT PER TILE, no LDS and no
-//    barriers.  The wavefront keeps the tile's 32 query rows in registers as MFMA operands (one
+//  * scan_wave_kernel (rows of 512 / 1024 / 1536 bytes): ONE WAVEFRONT PER TILE, no barriers.  The wavefront keeps the tile's 32 query rows in registers as MFMA operands (one
 //    wavefront per SIMD, so it owns all 512 vector registers) and streams the list through a
 //    register ring of RG 128-byte groups: while group g is multiplied, the 16-byte loads of the
 //    group RG steps ahead are in flight (16-24 KiB per wavefront, never drained at block or -- apart
 //    from the query load -- tile boundaries).  Wavefronts are independent workers on the tile queue,
-//    so nothing waits at a barrier for a slower neighbour.
+//    so nothing waits at a barrier for a slower neighbour.  The wavefront's own 33 KiB of LDS only
+//    stage the candidates that pass the filter.
 //  * scan_lds_kernel (any other row length): a workgroup of four wavefronts shares the tile's
 //    queries through LDS (row pitch = row bytes + 16: conflict-free 16-byte operand reads).
 //
@@ -39,8 +40,9 @@
 // of each of its 32 vectors.  Loads go through buffer descriptors sized to the chunk, so rows past
 // the end of a list and prefetches past its last block return zeros without touching memory and
 // the stream needs no branches.  The issue order is pinned with scheduling barriers, which lets the
-// compiler count outstanding loads exactly and wait only for the oldest ones.  Scores leave as
-// complete 128-byte lines (32 consecutive vectors of one query per half-wavefront store).
+// compiler count outstanding loads exactly and wait only for the oldest ones.  Dense scores (sample
+// launch) leave as complete 128-byte lines (32 consecutive vectors of one query per half-wavefront
+// store); filtered candidates leave in bursts (see scan_stage_block).
 #include "tri_common.h"
 #include "tri_mfma.h"
 

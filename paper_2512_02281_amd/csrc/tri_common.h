@@ -39,7 +39,7 @@ struct TriSlotMeta {
 struct TriNewDesc {
     uint32_t slot, index, metric, k, nprobe;
     uint32_t row_off;   // byte offset of its padded row inside the step's row area
-    uint64_t src_dev;   // 0: the row was uploaded; else device address of the caller's unpadded vector
+    uint64_t src_dev;   // GPU address of the query's vector: a row of the pool's pinned query store, or the caller's device vector
 };
 
 // One running slot's share of this step.
