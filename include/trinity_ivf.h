@@ -180,11 +180,13 @@ typedef struct {
     uint32_t finished;    /* tickets whose results became pollable during this call                 */
 } tri_step_stats;
 
-/* One step: admit (high class first, FIFO inside a class) -> coarse ranking of the admitted
- * queries -> pack the work items of all running queries (items of queries admitted in this
- * very call included; higher class first when W is short) -> list scan -> per-query top-k
- * merge -> retire.  Only enqueues GPU work and returns; results of the retired queries become
- * pollable when that work completes.  A call with nothing to do is a no-op. */
+/* One step: admit (by the policy in force, see tri_policy; default: high class first, FIFO
+ * inside a class) -> coarse ranking of the admitted queries -> pack the work items of all
+ * running queries (items of queries admitted in this very call included; higher class first
+ * when W is short) -> per-query thresholds from a sample of every probed list -> list scan,
+ * keeping what is not beyond the thresholds (which never costs a true result) -> per-query
+ * top-k merge -> retire.  Only enqueues GPU work and returns; results of the retired queries
+ * become pollable when that work completes.  A call with nothing to do is a no-op. */
 int search_step(tri_pool *pool, tri_step_stats *stats /*[host] out or NULL*/);
 
 /* Result of a finished query, best first (L2 ascending, IP descending; equal scores by
