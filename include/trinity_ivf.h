@@ -50,8 +50,7 @@ typedef enum {
 enum { TRI_L2 = 0, TRI_IP = 1 };          /* metric: squared L2 (smaller = better), inner product (larger = better) */
 enum { TRI_F32 = 0, TRI_F16 = 1 };        /* storage type of an index's vectors and of its queries                  */
 enum { TRI_CLASS_HIGH = 0, TRI_CLASS_LOW = 1 }; /* Sec. 3.3: prefill-side (latency critical) / decode-side requests */
-enum { TRI_FLAG_PROFILE = 1u,             /* bracket every stage of a step with HIP events (tri_pool_kernel_times);
-                                             the seven events cost about a quarter of a millisecond per step         */
+enum { TRI_FLAG_PROFILE = 1u,             /* bracket every stage of a step with HIP events (tri_pool_kernel_times)    */
        TRI_FLAG_KEEP_PROBES = 2u,         /* copy each query's probe list back so search_probes() can return it      */
        TRI_FLAG_PROFILE_SCAN = 4u };      /* bracket only the list scan (two events): scan_ms and the scan_* counters
                                              of tri_pool_kernel_times are filled, the other stage times stay zero    */
@@ -83,7 +82,8 @@ int tri_pool_workspace_bytes(const tri_pool_cfg *cfg /*[host]*/, size_t *dev_byt
 
 /* Create a pool on the current HIP device.  dev_ws [device]: at least the size reported above,
  * owned by the pool until tri_pool_destroy (the caller frees it afterwards).  Pinned host
- * staging is allocated here (hipHostMalloc); no device memory is allocated by the pool. */
+ * memory is allocated here (hipHostMalloc): upload and result blocks for the steps in flight and
+ * a store of max_outstanding padded query rows; no device memory is allocated by the pool. */
 int tri_pool_create(const tri_pool_cfg *cfg /*[host]*/, void *dev_ws /*[device]*/, size_t dev_ws_bytes,
                     tri_pool **out /*[host] out*/);
 
