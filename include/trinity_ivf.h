@@ -52,8 +52,15 @@ enum { TRI_F32 = 0, TRI_F16 = 1 };        /* storage type of an index's vectors 
 enum { TRI_CLASS_HIGH = 0, TRI_CLASS_LOW = 1 }; /* Sec. 3.3: prefill-side (latency critical) / decode-side requests */
 enum { TRI_FLAG_PROFILE = 1u,             /* bracket every stage of a step with HIP events (tri_pool_kernel_times)    */
        TRI_FLAG_KEEP_PROBES = 2u,         /* copy each query's probe list back so search_probes() can return it      */
-       TRI_FLAG_PROFILE_SCAN = 4u };      /* bracket only the list scan (two events): scan_ms and the scan_* counters
+       TRI_FLAG_PROFILE_SCAN = 4u,        /* bracket only the list scan (two events): scan_ms and the scan_* counters
                                              of tri_pool_kernel_times are filled, the other stage times stay zero    */
+       TRI_FLAG_GRAPH = 8u };             /* Sec. 3.2 (fixed-shape step captured once, replayed): the launch sequence
+                                             of a step is recorded as a HIP graph at the pool's largest shape (once per
+                                             step in flight and set of attached indexes) and search_step replays it; what
+                                             a step holds travels in its upload block.  Needs hip_stream != the default
+                                             stream (TRI_EHIP from the first search_step otherwise).  Results are
+                                             identical to those without the flag.  Steps that are profiled
+                                             (TRI_FLAG_PROFILE*) are launched kernel by kernel.                        */
 
 /* Limits of this implementation (checked, TRI_EINVAL beyond them). */
 #define TRI_KMAX_LIMIT 1024u      /* largest k a pool can be configured for           */

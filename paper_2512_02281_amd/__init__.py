@@ -17,7 +17,7 @@ TRI_OK, TRI_EINVAL, TRI_ENOMEM, TRI_EAGAIN, TRI_EHIP, TRI_ENOENT = 0, -1, -2, -3
 TRI_L2, TRI_IP = 0, 1
 TRI_F32, TRI_F16 = 0, 1
 TRI_CLASS_HIGH, TRI_CLASS_LOW = 0, 1
-TRI_FLAG_PROFILE, TRI_FLAG_KEEP_PROBES, TRI_FLAG_PROFILE_SCAN = 1, 2, 4
+TRI_FLAG_PROFILE, TRI_FLAG_KEEP_PROBES, TRI_FLAG_PROFILE_SCAN, TRI_FLAG_GRAPH = 1, 2, 4, 8
 TRI_ORDER_FIFO, TRI_ORDER_SLACK = 0, 1
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
@@ -387,7 +387,9 @@ class Pool:
         if not torch.cuda.is_available():
             raise RuntimeError("no GPU: the search path has no CPU fallback")
         self.cfg = tri_pool_cfg(**cfg_fields)
-        self.cfg.hip_stream = torch.cuda.current_stream().cuda_stream
+        # (a step can only be recorded for replay on a stream of its own, never on the default stream)
+        self._stream = torch.cuda.Stream() if self.cfg.flags & TRI_FLAG_GRAPH else torch.cuda.current_stream()
+        self.cfg.hip_stream = self._stream.cuda_stream
         nbytes = tri_pool_workspace_bytes(self.cfg)
         self._ws = torch.empty(nbytes + 256, dtype=torch.uint8, device="cuda")
         ptr = (self._ws.data_ptr() + 255) // 256 * 256

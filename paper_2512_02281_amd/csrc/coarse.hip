@@ -25,14 +25,15 @@
 #define CG_PIECES ((CG_BM + CG_BN) * (CG_KB / 16) / 256)   // 16-byte pieces per thread and stage (6)
 #define CG_PIECES_A (CG_BM * (CG_KB / 16) / 256)             // of which A rows (4)
 
+extern __shared__ __attribute__((aligned(16))) uint8_t cg_lds[];
+
 template <int DT>
-__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) void coarse_gemm_kernel(
+__device__ __forceinline__ void coarse_gemm_tile(
     const uint8_t *__restrict__ A, uint32_t a_pitch, uint32_t M,
     const uint8_t *__restrict__ B, uint32_t b_pitch, const float *__restrict__ bnorm, uint32_t N,
     uint32_t k_bytes, const uint32_t *__restrict__ row_metric, uint32_t metric_stride, uint32_t fixed_metric,
     float *__restrict__ C, uint32_t ldc)
 {
-    extern __shared__ __attribute__((aligned(16))) uint8_t cg_lds[];
 
     const uint32_t tid = threadIdx.x;
     const uint32_t lane = tid & 63, wave = tid >> 6;
@@ -150,6 +151,70 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
             }
         }
     }
+}
+
+template <int DT>
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) void coarse_gemm_kernel(
+    const uint8_t *__restrict__ A, uint32_t a_pitch, uint32_t M,
+    const uint8_t *__restrict__ B, uint32_t b_pitch, const float *__restrict__ bnorm, uint32_t N,
+    uint32_t k_bytes, const uint32_t *__restrict__ row_metric, uint32_t metric_stride, uint32_t fixed_metric,
+    float *__restrict__ C, uint32_t ldc)
+{
+    coarse_gemm_tile<DT>(A, a_pitch, M, B, b_pitch, bnorm, N, k_bytes, row_metric, metric_stride, fixed_metric, C, ldc);
+}
+
+// The same contraction for group `gi` of a step's newly admitted queries: rows, index and count come
+// from the step's header, so the launch is the same whatever the step admits.  Workgroups beyond the
+// group's rows or the index's centroids, and launches whose storage type is not the index's, leave at once.
+template <int DT>
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) void coarse_gemm_step_kernel(
+    const uint8_t *__restrict__ upload, uint32_t gi, const TriIndexDev *__restrict__ indexes, float *__restrict__ C)
+{
+    const TriStepHdr *hdr = (const TriStepHdr *)upload;
+    if (gi >= hdr->n_groups) return;
+    const TriCoarseGroup g = hdr->group[gi];
+    const TriIndexDev &ix = indexes[g.index];
+    if (ix.dtype != (uint32_t)DT || blockIdx.y * CG_BM >= g.m || blockIdx.x * CG_BN >= ix.nlist) return;
+    const TriNewDesc *desc = (const TriNewDesc *)(upload + hdr->desc_off);
+    coarse_gemm_tile<DT>(upload + hdr->rows_off + g.row_off, ix.row_bytes, g.m, (const uint8_t *)ix.centroids,
+                         ix.row_bytes, ix.cnorm, ix.nlist, ix.row_bytes, &desc[g.first_new].metric,
+                         (uint32_t)(sizeof(TriNewDesc) / 4), 0u, C, (ix.nlist + 31u) / 32u * 32u);
+}
+
+static hipError_t cg_raise_lds(const void *fn, bool *done)
+{
+    if (*done) return hipSuccess;                  // (more LDS than a kernel gets by default)
+    const hipError_t e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, CG_LDS + CG_BM * 4);
+    if (e == hipSuccess) *done = true;
+    return e;
+}
+
+static bool g_cg_step_lds_set[2] = {false, false};
+
+// What the first step launch of each variant would set up, done ahead.
+hipError_t tri_coarse_prepare()
+{
+    hipError_t e = cg_raise_lds((const void *)coarse_gemm_step_kernel<TRI_DT_F32>, &g_cg_step_lds_set[0]);
+    if (e == hipSuccess) e = cg_raise_lds((const void *)coarse_gemm_step_kernel<TRI_DT_F16>, &g_cg_step_lds_set[1]);
+    return e;
+}
+
+hipError_t tri_launch_coarse_gemm_step(const TriLaunchCtx &c, const TriDevWs &ws, int dtype, uint32_t group,
+                                       uint32_t grid_m, uint32_t grid_n)
+{
+    if (grid_m == 0 || grid_n == 0) return hipSuccess;
+    const int v = dtype == TRI_DT_F16 ? 1 : 0;
+    const void *fn = v ? (const void *)coarse_gemm_step_kernel<TRI_DT_F16> : (const void *)coarse_gemm_step_kernel<TRI_DT_F32>;
+    const hipError_t e = cg_raise_lds(fn, &g_cg_step_lds_set[v]);
+    if (e != hipSuccess) return e;
+    const dim3 grid((grid_n + CG_BN - 1) / CG_BN, (grid_m + CG_BM - 1) / CG_BM);
+    if (v)
+        hipLaunchKernelGGL(coarse_gemm_step_kernel<TRI_DT_F16>, grid, dim3(256), CG_LDS + CG_BM * 4, c.stream, ws.upload,
+                           group, ws.indexes, ws.coarse_scores);
+    else
+        hipLaunchKernelGGL(coarse_gemm_step_kernel<TRI_DT_F32>, grid, dim3(256), CG_LDS + CG_BM * 4, c.stream, ws.upload,
+                           group, ws.indexes, ws.coarse_scores);
+    return hipGetLastError();
 }
 
 hipError_t tri_launch_coarse_gemm(hipStream_t s, int dtype, const void *a_rows, uint32_t a_pitch_bytes, uint32_t m,

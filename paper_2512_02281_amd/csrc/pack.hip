@@ -16,19 +16,21 @@ __global__ void fill_u32_kernel(uint32_t *p, uint32_t v, size_t n)
 
 // The step's upload block (admission records, plan), pulled from pinned host memory by a
 // kernel of the pool's own stream: it starts the moment the previous kernel ends, where a runtime copy
-// first spends tens of microseconds being set up.  16 bytes per thread and load.
-__global__ void pull_block_kernel(uint4 *__restrict__ dst, const uint4 *__restrict__ src_host, size_t n16)
+// first spends tens of microseconds being set up.  16 bytes per thread and load; how much there is to
+// pull stands in the block's own header (first word), so the launch does not depend on it.
+__global__ void pull_block_kernel(uint4 *__restrict__ dst, const uint4 *__restrict__ src_host)
 {
+    const size_t n16 = ((const TriStepHdr *)src_host)->n16;
     const size_t stride = (size_t)gridDim.x * blockDim.x;
     for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n16; i += stride) dst[i] = src_host[i];
 }
 
-hipError_t tri_launch_pull_block(hipStream_t s, void *dst_dev, const void *src_host_as_device, size_t bytes)
+hipError_t tri_launch_pull_block(hipStream_t s, void *dst_dev, const void *src_host_as_device, size_t grid_bytes)
 {
-    const size_t n16 = (bytes + 15) / 16;          // (both buffers are padded to 256 bytes)
+    const size_t n16 = (grid_bytes + 15) / 16;          // (both buffers are padded to 256 bytes)
     if (n16 == 0) return hipSuccess;
-    const unsigned blocks = (unsigned)std::min<size_t>((n16 + 255) / 256, 2048);
-    hipLaunchKernelGGL(pull_block_kernel, dim3(blocks), dim3(256), 0, s, (uint4 *)dst_dev, (const uint4 *)src_host_as_device, n16);
+    const unsigned blocks = (unsigned)std::min<size_t>((n16 + 255) / 256, 64);
+    hipLaunchKernelGGL(pull_block_kernel, dim3(blocks), dim3(256), 0, s, (uint4 *)dst_dev, (const uint4 *)src_host_as_device);
     return hipGetLastError();
 }
 
@@ -62,14 +64,17 @@ __device__ __forceinline__ float admit_row(const TriNewDesc &d, uint32_t dim, ui
     return part;
 }
 
-__global__ __launch_bounds__(256) void admit_kernel(const TriNewDesc *__restrict__ desc, uint8_t *__restrict__ rows,
+__global__ __launch_bounds__(256) void admit_kernel(uint8_t *__restrict__ upload,
                                                     const TriIndexDev *__restrict__ indexes,
                                                     uint8_t *__restrict__ slot_query, uint32_t slot_row_bytes,
                                                     TriSlotMeta *__restrict__ slot_meta,
                                                     float *__restrict__ slot_qnorm, uint32_t *__restrict__ topk_count)
 {
     __shared__ float red[256];
-    const TriNewDesc d = desc[blockIdx.x];
+    const TriStepHdr *hdr = (const TriStepHdr *)upload;
+    if (blockIdx.x >= hdr->n_new) return;
+    const TriNewDesc d = ((const TriNewDesc *)(upload + hdr->desc_off))[blockIdx.x];
+    uint8_t *rows = upload + hdr->rows_off;
     const TriIndexDev &ix = indexes[d.index];
     uint8_t *dst = slot_query + (size_t)d.slot * slot_row_bytes;
     const float part = ix.dtype == 1u ? admit_row<_Float16>(d, ix.dim, ix.dpad, rows, dst)
@@ -87,11 +92,10 @@ __global__ __launch_bounds__(256) void admit_kernel(const TriNewDesc *__restrict
     }
 }
 
-hipError_t tri_launch_admit(const TriLaunchCtx &c, const TriDevWs &ws, const TriNewDesc *desc_dev, uint8_t *rows_dev,
-                            uint32_t n_new)
+hipError_t tri_launch_admit(const TriLaunchCtx &c, const TriDevWs &ws, uint32_t grid_new)
 {
-    if (n_new == 0) return hipSuccess;
-    hipLaunchKernelGGL(admit_kernel, dim3(n_new), dim3(256), 0, c.stream, desc_dev, rows_dev, ws.indexes,
+    if (grid_new == 0) return hipSuccess;
+    hipLaunchKernelGGL(admit_kernel, dim3(grid_new), dim3(256), 0, c.stream, ws.upload, ws.indexes,
                        ws.slot_query, c.slot_row_bytes, ws.slot_meta, ws.slot_qnorm, ws.topk_count);
     return hipGetLastError();
 }
@@ -101,15 +105,17 @@ hipError_t tri_launch_admit(const TriLaunchCtx &c, const TriDevWs &ws, const Tri
 //     entries' item_base) is list probe[slot][cursor + j]; its rank inside the list's group is
 //     taken from an atomic counter.  The rank decides only which tile row a query occupies; every
 //     score is computed independently of its neighbours, so results do not depend on it.
-__global__ void pack_emit_kernel(const TriPlanEntry *__restrict__ plan, uint32_t n_plan, uint32_t n_items,
+__global__ void pack_emit_kernel(const uint8_t *__restrict__ upload,
                                  const TriSlotMeta *__restrict__ slot_meta, const TriIndexDev *__restrict__ indexes,
                                  const uint32_t *__restrict__ probe, uint32_t nprobe_max,
                                  uint32_t *__restrict__ item_glist, uint32_t *__restrict__ item_slot,
                                  uint32_t *__restrict__ item_rank, uint32_t *__restrict__ hist)
 {
+    const TriStepHdr *hdr = (const TriStepHdr *)upload;
+    const TriPlanEntry *plan = (const TriPlanEntry *)(upload + hdr->plan_off);
     const uint32_t i = blockIdx.x * blockDim.x + threadIdx.x;
-    if (i >= n_items) return;
-    uint32_t lo = 0, hi = n_plan;          // last entry with item_base <= i
+    if (i >= hdr->n_items) return;
+    uint32_t lo = 0, hi = hdr->n_plan;     // last entry with item_base <= i
     while (hi - lo > 1) {
         const uint32_t mid = (lo + hi) >> 1;
         if (plan[mid].item_base <= i) lo = mid; else hi = mid;
@@ -140,13 +146,15 @@ __global__ __launch_bounds__(1024) void pack_scan_kernel(const uint32_t *__restr
                                                          uint32_t *__restrict__ stile_base,
                                                          uint64_t *__restrict__ score_base,
                                                          TriStepDev *__restrict__ step_dev,
-                                                         uint32_t *__restrict__ tile_counter, uint32_t min_chunk,
+                                                         uint32_t *__restrict__ tile_counter,
+                                                         const TriStepHdr *__restrict__ hdr,
                                                          uint64_t *__restrict__ block_tot,
                                                          TriStepDev *__restrict__ step_host)
 {
     __shared__ uint32_t s_items[1024], s_tiles[1024], s_lists[1024], s_stiles[1024];
     __shared__ uint64_t s_scores[1024], s_tbytes[1024], s_ubytes[1024];
     const uint32_t t = threadIdx.x;
+    const uint32_t min_chunk = hdr->min_chunk;
     const uint32_t span = (n_order + gridDim.x - 1) / gridDim.x;
     const uint32_t s0 = min(blockIdx.x * span, n_order), s1 = min(s0 + span, n_order);
     const uint32_t per = (span + 1023) / 1024;
@@ -246,14 +254,14 @@ __global__ __launch_bounds__(1024) void pack_scan_kernel(const uint32_t *__restr
 }
 
 // (3) scatter: one thread per item -> list-sorted slot array and the item's score segment.
-__global__ void pack_scatter_kernel(uint32_t n_items, const uint32_t *__restrict__ item_glist,
+__global__ void pack_scatter_kernel(const TriStepHdr *__restrict__ hdr, const uint32_t *__restrict__ item_glist,
                                     const uint32_t *__restrict__ item_slot, const uint32_t *__restrict__ item_rank,
                                     const uint32_t *__restrict__ list_start, const uint64_t *__restrict__ score_base,
                                     const uint32_t *__restrict__ glist_len, uint32_t *__restrict__ sorted_slot,
                                     uint64_t *__restrict__ item_score_off, uint32_t *__restrict__ item_sorted_pos)
 {
     const uint32_t i = blockIdx.x * blockDim.x + threadIdx.x;
-    if (i >= n_items) return;
+    if (i >= hdr->n_items) return;
     const uint32_t g = item_glist[i], r = item_rank[i];
     const uint32_t npad = (glist_len[g] + TRI_VB - 1) / TRI_VB * TRI_VB;
     sorted_slot[list_start[g] + r] = item_slot[i];
@@ -269,10 +277,12 @@ __global__ void pack_tiles_kernel(uint32_t total_lists, const uint32_t *__restri
                                   const uint32_t *__restrict__ stile_base, const uint64_t *__restrict__ score_base,
                                   const uint32_t *__restrict__ glist_len, const uint32_t *__restrict__ glist_voff,
                                   const uint32_t *__restrict__ glist_index, const TriIndexDev *__restrict__ indexes,
-                                  uint32_t min_chunk, TriTile *__restrict__ tiles, TriTile *__restrict__ stiles)
+                                  const TriStepHdr *__restrict__ hdr, TriTile *__restrict__ tiles,
+                                  TriTile *__restrict__ stiles)
 {
     const uint32_t g = blockIdx.x * blockDim.x + threadIdx.x;
     if (g >= total_lists) return;
+    const uint32_t min_chunk = hdr->min_chunk;
     const uint32_t c = hist[g];
     const uint32_t len = glist_len[g];
     if (!c || !len) return;
@@ -316,28 +326,31 @@ __global__ void pack_tiles_kernel(uint32_t total_lists, const uint32_t *__restri
     }
 }
 
-hipError_t tri_launch_pack(const TriLaunchCtx &c, const TriDevWs &ws, const TriPlanEntry *plan_dev, uint32_t n_plan,
-                           uint32_t n_items, uint32_t total_lists, uint32_t n_order, uint32_t min_chunk)
+hipError_t tri_launch_pack(const TriLaunchCtx &c, const TriDevWs &ws, uint32_t grid_items, uint32_t total_lists,
+                           uint32_t n_order)
 {
-    if (n_items == 0 || total_lists == 0) return hipSuccess;
+    if (total_lists == 0) return hipSuccess;
+    const TriStepHdr *hdr = (const TriStepHdr *)ws.upload;
     hipError_t e = tri_launch_fill_u32(c.stream, ws.hist, 0u, total_lists);
     if (e != hipSuccess) return e;
-    hipLaunchKernelGGL(pack_emit_kernel, dim3((n_items + 255) / 256), dim3(256), 0, c.stream, plan_dev, n_plan,
-                       n_items, ws.slot_meta, ws.indexes, ws.probe, c.nprobe_max, ws.item_glist, ws.item_slot,
-                       ws.item_rank, ws.hist);
+    if (grid_items)
+        hipLaunchKernelGGL(pack_emit_kernel, dim3((grid_items + 255) / 256), dim3(256), 0, c.stream, ws.upload,
+                           ws.slot_meta, ws.indexes, ws.probe, c.nprobe_max, ws.item_glist, ws.item_slot,
+                           ws.item_rank, ws.hist);
     const uint32_t nb = std::min<uint32_t>(PACK_SCAN_BLOCKS, (n_order + 1023) / 1024);
     if (nb > 1)
         hipLaunchKernelGGL(pack_scan_kernel<false>, dim3(nb), dim3(1024), 0, c.stream, ws.hist, n_order, ws.glist_order,
                            ws.list_start, ws.tile_base, ws.stile_base, ws.score_base, ws.step_dev, ws.tile_counter,
-                           min_chunk, ws.pack_tot, (TriStepDev *)nullptr);
+                           hdr, ws.pack_tot, (TriStepDev *)nullptr);
     hipLaunchKernelGGL(pack_scan_kernel<true>, dim3(nb ? nb : 1), dim3(1024), 0, c.stream, ws.hist, n_order, ws.glist_order,
-                       ws.list_start, ws.tile_base, ws.stile_base, ws.score_base, ws.step_dev, ws.tile_counter, min_chunk,
+                       ws.list_start, ws.tile_base, ws.stile_base, ws.score_base, ws.step_dev, ws.tile_counter, hdr,
                        ws.pack_tot, ws.step_host);
-    hipLaunchKernelGGL(pack_scatter_kernel, dim3((n_items + 255) / 256), dim3(256), 0, c.stream, n_items,
-                       ws.item_glist, ws.item_slot, ws.item_rank, ws.list_start, ws.score_base, ws.glist_len,
-                       ws.sorted_slot, ws.item_score_off, ws.item_sorted_pos);
+    if (grid_items)
+        hipLaunchKernelGGL(pack_scatter_kernel, dim3((grid_items + 255) / 256), dim3(256), 0, c.stream, hdr,
+                           ws.item_glist, ws.item_slot, ws.item_rank, ws.list_start, ws.score_base, ws.glist_len,
+                           ws.sorted_slot, ws.item_score_off, ws.item_sorted_pos);
     hipLaunchKernelGGL(pack_tiles_kernel, dim3((total_lists + 255) / 256), dim3(256), 0, c.stream, total_lists,
                        ws.hist, ws.list_start, ws.tile_base, ws.stile_base, ws.score_base, ws.glist_len, ws.glist_voff,
-                       ws.glist_index, ws.indexes, min_chunk, ws.tiles, ws.stiles);
+                       ws.glist_index, ws.indexes, hdr, ws.tiles, ws.stiles);
     return hipGetLastError();
 }

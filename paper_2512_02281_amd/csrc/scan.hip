@@ -523,6 +523,35 @@ static ScanVariant scan_variant(uint32_t klass)
 
 static uint32_t g_scan_lds_limit[2 * TRI_SCAN_CLASSES] = {};
 
+// LDS of the workgroup kernels: the query tile at the widest attached row length; a kernel's limit is
+// raised (once per growth) before it is first launched with that much.
+static uint32_t scan_lds_bytes(uint32_t max_row_bytes) { return TRI_QT * (max_row_bytes + 16); }
+
+static hipError_t scan_raise_lds(const ScanVariant &v, uint32_t slot, uint32_t lds)
+{
+    uint32_t &limit = g_scan_lds_limit[slot];
+    if (lds <= limit) return hipSuccess;
+    const hipError_t e = hipFuncSetAttribute((const void *)v.fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    if (e == hipSuccess) limit = lds;
+    return e;
+}
+
+// Everything tri_launch_scan would set up on first use, done ahead (so that a recording of the launches
+// holds nothing but launches).
+hipError_t tri_scan_prepare(uint32_t max_row_bytes, uint32_t class_mask)
+{
+    for (uint32_t k = 0; k < TRI_SCAN_CLASSES; ++k) {
+        if (!(class_mask & (1u << k))) continue;
+        for (int sample = 0; sample < 2; ++sample) {
+            const ScanVariant v = sample ? scan_variant<false>(k) : scan_variant<true>(k);
+            if (v.wave) continue;
+            const hipError_t e = scan_raise_lds(v, (sample ? TRI_SCAN_CLASSES : 0) + k, scan_lds_bytes(max_row_bytes));
+            if (e != hipSuccess) return e;
+        }
+    }
+    return hipSuccess;
+}
+
 // Launch the scan kernels of one step -- the sample launch or the main launch -- one kernel per class
 // present in class_mask, each a persistent grid sized to what the chip holds at once.
 hipError_t tri_launch_scan(const TriLaunchCtx &c, const TriDevWs &ws, uint32_t max_row_bytes, uint32_t class_mask,
@@ -541,15 +570,11 @@ hipError_t tri_launch_scan(const TriLaunchCtx &c, const TriDevWs &ws, uint32_t m
                                ws.slot_query, c.slot_row_bytes, c.S, ws.slot_meta, ws.slot_qnorm, ws.thr_key,
                                ws.surv_count, out);
         } else {
-            const uint32_t lds = TRI_QT * (max_row_bytes + 16);
+            const uint32_t lds = scan_lds_bytes(max_row_bytes);
             uint32_t per_cu = (160u * 1024u - 1024u) / (lds + 1024u);
             per_cu = per_cu < 1 ? 1 : (per_cu > 3 ? 3 : per_cu);
-            uint32_t &limit = g_scan_lds_limit[(sample ? TRI_SCAN_CLASSES : 0) + k];
-            if (lds > limit) {
-                hipError_t e = hipFuncSetAttribute((const void *)v.fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-                if (e != hipSuccess) return e;
-                limit = lds;
-            }
+            const hipError_t e = scan_raise_lds(v, (sample ? TRI_SCAN_CLASSES : 0) + k, lds);
+            if (e != hipSuccess) return e;
             hipLaunchKernelGGL(v.fn, dim3(c.n_cu * per_cu), dim3(TRI_SCAN_THREADS), lds, c.stream, tiles, n_ptr, counter,
                                k, ws.sorted_slot, ws.slot_query, c.slot_row_bytes, c.S, ws.slot_meta, ws.slot_qnorm,
                                ws.thr_key, ws.surv_count, out);

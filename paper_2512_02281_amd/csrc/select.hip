@@ -544,11 +544,17 @@ __device__ const uint64_t *sel_block_topk(SelShared &sh, const SelSrc &src, SegF
 #define CSEL_PER 64        // scores per thread the fast path holds in registers: rows of up to 16384 centroids
 
 __global__ __launch_bounds__(TRI_SEL_THREADS) void coarse_select_kernel(
-    const float *__restrict__ scores, uint32_t ldc, uint32_t nlist, const TriNewDesc *__restrict__ desc,
-    uint32_t first_new, uint32_t *__restrict__ probe, uint32_t nprobe_max)
+    const float *__restrict__ scores, const uint8_t *__restrict__ upload, uint32_t gi,
+    const TriIndexDev *__restrict__ indexes, uint32_t *__restrict__ probe, uint32_t nprobe_max)
 {
     __shared__ SelShared sh;
-    const TriNewDesc d = desc[first_new + blockIdx.x];
+    // (group gi of the step's header: which admission records, which index; surplus workgroups leave)
+    const TriStepHdr *hdr = (const TriStepHdr *)upload;
+    if (gi >= hdr->n_groups) return;
+    const TriCoarseGroup g = hdr->group[gi];
+    if (blockIdx.x >= g.m) return;
+    const uint32_t nlist = indexes[g.index].nlist, ldc = (nlist + 31u) / 32u * 32u;
+    const TriNewDesc d = ((const TriNewDesc *)(upload + hdr->desc_off))[g.first_new + blockIdx.x];
     const float *row = scores + (size_t)blockIdx.x * ldc;
     uint32_t *dst = probe + (size_t)d.slot * nprobe_max;
     const uint32_t tid = threadIdx.x;
@@ -608,12 +614,11 @@ __global__ __launch_bounds__(TRI_SEL_THREADS) void coarse_select_kernel(
     for (uint32_t i = tid; i < n; i += TRI_SEL_THREADS) dst[i] = (uint32_t)(best[i] & 0xFFFFFFFFu);
 }
 
-hipError_t tri_launch_coarse_select(const TriLaunchCtx &c, const TriDevWs &ws, const TriNewDesc *desc_dev,
-                                    uint32_t first_new, uint32_t m, uint32_t nlist, uint32_t ldc)
+hipError_t tri_launch_coarse_select(const TriLaunchCtx &c, const TriDevWs &ws, uint32_t group, uint32_t grid_m)
 {
-    if (m == 0) return hipSuccess;
-    hipLaunchKernelGGL(coarse_select_kernel, dim3(m), dim3(TRI_SEL_THREADS), 0, c.stream, ws.coarse_scores, ldc,
-                       nlist, desc_dev, first_new, ws.probe, c.nprobe_max);
+    if (grid_m == 0) return hipSuccess;
+    hipLaunchKernelGGL(coarse_select_kernel, dim3(grid_m), dim3(TRI_SEL_THREADS), 0, c.stream, ws.coarse_scores,
+                       ws.upload, group, ws.indexes, ws.probe, c.nprobe_max);
     return hipGetLastError();
 }
 
@@ -623,7 +628,7 @@ hipError_t tri_launch_coarse_select(const TriLaunchCtx &c, const TriDevWs &ws, c
 // running top-k -- a subset of its candidates, so nothing of its final top-k lies beyond it.  Fewer
 // than k such keys: no filtering (all-ones).
 __global__ __launch_bounds__(TRI_SEL_THREADS) void slot_threshold_kernel(
-    const TriPlanEntry *__restrict__ plan, const TriSlotMeta *__restrict__ slot_meta,
+    const uint8_t *__restrict__ upload, const TriSlotMeta *__restrict__ slot_meta,
     const uint32_t *__restrict__ item_glist, const uint32_t *__restrict__ item_sorted_pos,
     const uint32_t *__restrict__ glist_len, const float *__restrict__ sample_scores,
     const float *__restrict__ topk_score, const uint32_t *__restrict__ topk_count, uint32_t kmax,
@@ -632,7 +637,9 @@ __global__ __launch_bounds__(TRI_SEL_THREADS) void slot_threshold_kernel(
 {
     static_assert(TRI_SAMPLE_VECS == TRI_VB && TRI_SAMPLE_VECS == 32, "the sample is the first block of a list");
     __shared__ SelShared sh;
-    const TriPlanEntry e = plan[blockIdx.x];
+    const TriStepHdr *hdr = (const TriStepHdr *)upload;
+    if (blockIdx.x >= hdr->n_plan) return;
+    const TriPlanEntry e = ((const TriPlanEntry *)(upload + hdr->plan_off))[blockIdx.x];
     const TriSlotMeta meta = slot_meta[e.slot];
     const uint32_t desc = meta.metric == 1u;
     const uint32_t have = e.cursor > 0 ? topk_count[e.slot] : 0u;
@@ -696,10 +703,10 @@ __global__ __launch_bounds__(TRI_SEL_THREADS) void slot_threshold_kernel(
     }
 }
 
-hipError_t tri_launch_threshold(const TriLaunchCtx &c, const TriDevWs &ws, const TriPlanEntry *plan_dev, uint32_t n_plan)
+hipError_t tri_launch_threshold(const TriLaunchCtx &c, const TriDevWs &ws, uint32_t grid_plan)
 {
-    if (n_plan == 0) return hipSuccess;
-    hipLaunchKernelGGL(slot_threshold_kernel, dim3(n_plan), dim3(TRI_SEL_THREADS), 0, c.stream, plan_dev, ws.slot_meta,
+    if (grid_plan == 0) return hipSuccess;
+    hipLaunchKernelGGL(slot_threshold_kernel, dim3(grid_plan), dim3(TRI_SEL_THREADS), 0, c.stream, ws.upload, ws.slot_meta,
                        ws.item_glist, ws.item_sorted_pos, ws.glist_len, ws.sample_scores, ws.topk_score, ws.topk_count,
                        c.kmax, ws.thr_key, ws.item_score_off, ws.scores, ws.surv_count);
     return hipGetLastError();
@@ -710,17 +717,20 @@ hipError_t tri_launch_threshold(const TriLaunchCtx &c, const TriDevWs &ws, const
 // the scan kept for the slot's work items of this step, one segment per (item, chunk), + its running
 // top-k.  Output = new running top-k, or -- when the slot retires in this step -- its final result.
 __global__ __launch_bounds__(TRI_SEL_THREADS) void slot_merge_kernel(
-    const TriPlanEntry *__restrict__ plan, const TriSlotMeta *__restrict__ slot_meta,
+    const uint8_t *__restrict__ upload, const TriSlotMeta *__restrict__ slot_meta,
     const TriIndexDev *__restrict__ indexes, const uint32_t *__restrict__ item_glist,
     const uint64_t *__restrict__ item_score_off, const uint32_t *__restrict__ item_sorted_pos,
-    const uint32_t *__restrict__ surv_count, uint32_t min_chunk, const uint32_t *__restrict__ glist_len,
+    const uint32_t *__restrict__ surv_count, const uint32_t *__restrict__ glist_len,
     const uint32_t *__restrict__ glist_voff, const float *__restrict__ cand, float *__restrict__ topk_score,
     uint32_t *__restrict__ topk_id, uint32_t *__restrict__ topk_count, uint32_t kmax,
     uint32_t *__restrict__ res_block, const uint32_t *__restrict__ probe, uint32_t nprobe_max,
     uint32_t *__restrict__ res_probes)
 {
     __shared__ SelShared sh;
-    const TriPlanEntry e = plan[blockIdx.x];
+    const TriStepHdr *hdr = (const TriStepHdr *)upload;
+    if (blockIdx.x >= hdr->n_plan) return;
+    const uint32_t min_chunk = hdr->min_chunk;
+    const TriPlanEntry e = ((const TriPlanEntry *)(upload + hdr->plan_off))[blockIdx.x];
     const TriSlotMeta meta = slot_meta[e.slot];
     const uint32_t desc = meta.metric == 1u;
     const uint32_t have = e.cursor > 0 ? topk_count[e.slot] : 0u;
@@ -765,12 +775,11 @@ __global__ __launch_bounds__(TRI_SEL_THREADS) void slot_merge_kernel(
     }
 }
 
-hipError_t tri_launch_merge(const TriLaunchCtx &c, const TriDevWs &ws, const TriPlanEntry *plan_dev, uint32_t n_plan,
-                            bool keep_probes, uint32_t min_chunk)
+hipError_t tri_launch_merge(const TriLaunchCtx &c, const TriDevWs &ws, uint32_t grid_plan, bool keep_probes)
 {
-    if (n_plan == 0) return hipSuccess;
-    hipLaunchKernelGGL(slot_merge_kernel, dim3(n_plan), dim3(TRI_SEL_THREADS), 0, c.stream, plan_dev, ws.slot_meta,
-                       ws.indexes, ws.item_glist, ws.item_score_off, ws.item_sorted_pos, ws.surv_count, min_chunk,
+    if (grid_plan == 0) return hipSuccess;
+    hipLaunchKernelGGL(slot_merge_kernel, dim3(grid_plan), dim3(TRI_SEL_THREADS), 0, c.stream, ws.upload, ws.slot_meta,
+                       ws.indexes, ws.item_glist, ws.item_score_off, ws.item_sorted_pos, ws.surv_count,
                        ws.glist_len, ws.glist_voff, ws.scores, ws.topk_score, ws.topk_id, ws.topk_count, c.kmax,
                        ws.res_block, ws.probe, c.nprobe_max, keep_probes ? ws.res_probes : (uint32_t *)nullptr);
     return hipGetLastError();

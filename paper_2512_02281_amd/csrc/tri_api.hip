@@ -104,6 +104,8 @@ struct StepRec {
     std::vector<uint32_t> retire;     // ticket index per retire_idx
     uint32_t n_items = 0;
     bool had_scan = false;
+    hipGraph_t graph = nullptr;       // TRI_FLAG_GRAPH: the step's launch sequence with this entry's pinned blocks,
+    hipGraphExec_t graph_exec = nullptr;   // recorded once (per set of attached indexes) and replayed
 };
 
 }  // namespace
@@ -156,6 +158,7 @@ struct tri_pool {
     tri_kernel_times times{};
     // scratch vectors reused by search_step
     std::vector<uint32_t> order, newq;
+    std::vector<uint8_t> index_seen;      // per attached index: has a query been admitted for it in this step
     std::vector<uint32_t> run_order[2];   // running slots per class, in admission order (with the admission number
     std::vector<uint64_t> run_seq[2];     //   each had then: a slot number alone could be a later occupant)
     // scheduling policy (Sec. 3.3) and the measured mean step duration its slack order uses
@@ -168,6 +171,8 @@ struct tri_pool {
 };
 
 namespace {
+
+void drop_graphs(tri_pool *P);
 
 // Carve the device workspace.  Must match TriDevWs field for field.
 size_t carve(const tri_pool_cfg &c, uint32_t max_row_bytes, uint32_t coarse_rows, uint32_t coarse_ldc,
@@ -247,7 +252,7 @@ int derive(const tri_pool_cfg *c, uint32_t *max_row_bytes, uint32_t *coarse_rows
     *score_capacity = c->score_capacity ? c->score_capacity : (uint64_t)c->items_per_step * 2048u;
     if (*score_capacity > (1ull << 32))      // candidate pairs are addressed with 32-bit pair numbers
         return fail(TRI_EINVAL, "score_capacity must not exceed 2^32 words");
-    *upload_bytes = round_up_sz((size_t)c->slots * sizeof(TriNewDesc), 256) +
+    *upload_bytes = sizeof(TriStepHdr) + round_up_sz((size_t)c->slots * sizeof(TriNewDesc), 256) +
                     round_up_sz((size_t)c->slots * sizeof(TriPlanEntry), 256) + (size_t)c->slots * *max_row_bytes;
     return TRI_OK;
 }
@@ -508,7 +513,7 @@ extern "C" int tri_pool_destroy(tri_pool *P)
     if (!P) return fail(TRI_EINVAL, "pool is NULL");
     for (tri_index *ix : P->indexes)
         if (ix) return fail(TRI_EINVAL, "destroy the pool's indexes first");
-    (void)hipStreamSynchronize(P->stream);
+    drop_graphs(P);
     for (uint32_t i = 0; i < RING; ++i) {
         if (P->ring[i].done) (void)hipEventDestroy(P->ring[i].done);
         for (uint32_t j = 0; j < N_EV; ++j)
@@ -744,6 +749,7 @@ extern "C" int ivf_build(tri_pool *P, const ivf_params *p, const void *base, uin
     P->total_lists += nlist;
     P->attached_row_bytes = std::max(P->attached_row_bytes, rb);
     P->scan_class_mask |= 1u << tri_scan_class(p->dtype, rb);
+    drop_graphs(P);                    // (recorded steps cover the indexes attached when they were recorded)
     *out = ix;
     return TRI_OK;
 }
@@ -809,6 +815,7 @@ extern "C" int ivf_destroy(tri_index *ix)
         }
     if (ix->list_base + ix->p.nlist == P->total_lists) P->total_lists = ix->list_base;   // last attached: give its list range back
     delete ix;
+    drop_graphs(P);
     return upload_scan_order(P);
 }
 
@@ -876,6 +883,72 @@ extern "C" int search_submit(tri_pool *P, const tri_query *q, tri_ticket *out)
     return search_submit_batch(P, q, 1, out, nullptr);
 }
 
+namespace {
+
+// Forget the recorded steps (the attached indexes changed, or the pool goes away).
+void drop_graphs(tri_pool *P)
+{
+    (void)hipStreamSynchronize(P->stream);
+    for (uint32_t i = 0; i < RING; ++i) {
+        StepRec &R = P->ring[i];
+        if (R.graph_exec) (void)hipGraphExecDestroy(R.graph_exec);
+        if (R.graph) (void)hipGraphDestroy(R.graph);
+        R.graph_exec = nullptr;
+        R.graph = nullptr;
+    }
+}
+
+// Record the launch sequence of a step that uses ring entry R (its pinned upload and result blocks) at
+// the largest shape the pool allows: every slot admitted and running, W items, every coarse group,
+// every scan kernel variant the attached indexes need.  The kernels take what a step really holds from
+// its header, so one recording serves every later step until the set of attached indexes changes.
+int record_step(tri_pool *P, StepRec &R, const TriDevWs &W, bool keep_probes)
+{
+    const tri_pool_cfg &cfg = P->cfg;
+    hipStream_t s = P->stream;
+    uint32_t n_attached = 0, nlist_of[2] = {0, 0};
+    for (const tri_index *ix : P->indexes)
+        if (ix) {
+            ++n_attached;
+            nlist_of[ix->p.dtype == TRI_F16] = std::max(nlist_of[ix->p.dtype == TRI_F16], ix->p.nlist);
+        }
+    const uint32_t max_groups = std::min<uint32_t>(TRI_MAX_COARSE_GROUPS, n_attached + cfg.slots / P->coarse_rows);
+    hipError_t e = tri_scan_prepare(P->attached_row_bytes, P->scan_class_mask);
+    if (e == hipSuccess) e = tri_coarse_prepare();
+    if (e != hipSuccess) return fail(TRI_EHIP, "kernel set-up -> %s", hipGetErrorString(e));
+    e = hipStreamBeginCapture(s, hipStreamCaptureModeThreadLocal);
+    if (e != hipSuccess) return fail(TRI_EHIP, "hipStreamBeginCapture -> %s (a pool with TRI_FLAG_GRAPH needs a stream of its own, not the default stream)", hipGetErrorString(e));
+    e = tri_launch_pull_block(s, P->ws.upload, R.up_dev, P->upload_bytes - (size_t)cfg.slots * P->max_row_bytes);
+    if (e == hipSuccess) e = tri_launch_admit(P->ctx, P->ws, cfg.slots);
+    for (uint32_t g = 0; g < max_groups && e == hipSuccess; ++g) {
+        for (int dt = 0; dt < 2 && e == hipSuccess; ++dt)
+            if (nlist_of[dt]) e = tri_launch_coarse_gemm_step(P->ctx, P->ws, dt ? TRI_F16 : TRI_F32, g, P->coarse_rows, nlist_of[dt]);
+        if (e == hipSuccess) e = tri_launch_coarse_select(P->ctx, P->ws, g, P->coarse_rows);
+    }
+    if (e == hipSuccess) e = tri_launch_pack(P->ctx, W, cfg.items_per_step, P->total_lists, P->n_order);
+    if (e == hipSuccess) e = tri_launch_scan(P->ctx, P->ws, P->attached_row_bytes, P->scan_class_mask, true);
+    if (e == hipSuccess) e = tri_launch_threshold(P->ctx, P->ws, cfg.slots);
+    if (e == hipSuccess) e = tri_launch_scan(P->ctx, P->ws, P->attached_row_bytes, P->scan_class_mask, false);
+    if (e == hipSuccess) e = tri_launch_merge(P->ctx, W, cfg.slots, keep_probes);
+    hipGraph_t g = nullptr;
+    const hipError_t e2 = hipStreamEndCapture(s, &g);      // (always: a stream must not be left capturing)
+    if (e != hipSuccess || e2 != hipSuccess) {
+        if (g) (void)hipGraphDestroy(g);
+        return fail(TRI_EHIP, "recording the step -> %s", hipGetErrorString(e != hipSuccess ? e : e2));
+    }
+    hipGraphExec_t x = nullptr;
+    e = hipGraphInstantiate(&x, g, nullptr, nullptr, 0);
+    if (e != hipSuccess) {
+        (void)hipGraphDestroy(g);
+        return fail(TRI_EHIP, "hipGraphInstantiate -> %s", hipGetErrorString(e));
+    }
+    R.graph = g;
+    R.graph_exec = x;
+    return TRI_OK;
+}
+
+}  // namespace
+
 extern "C" int search_step(tri_pool *P, tri_step_stats *st)
 {
     if (!P) return fail(TRI_EINVAL, "pool is NULL");
@@ -891,11 +964,14 @@ extern "C" int search_step(tri_pool *P, tri_step_stats *st)
         if (rc) return rc;
     }
     const tri_pool_cfg &cfg = P->cfg;
-    TriNewDesc *desc_h = (TriNewDesc *)R.up_host;
 
     // ---- admit (Sec. 3.3): the free slots are split between the classes by the reserved share, the
     //      high class is taken in arrival or least-slack order, the low class first-in first-out
     P->newq.clear();
+    // (the admitted queries are ranked in groups of one index and at most coarse_rows rows; a step's
+    // header has room for TRI_MAX_COARSE_GROUPS of them, so admission stops where more could be needed)
+    P->index_seen.assign(cfg.max_indexes, 0);
+    uint32_t n_distinct = 0;
     {
         uint32_t take[2] = {0, 0};
         tri_policy_split((uint32_t)P->free_slots.size(), (uint32_t)P->pending[0].size(), (uint32_t)P->pending[1].size(),
@@ -919,6 +995,13 @@ extern "C" int search_step(tri_pool *P, tri_step_stats *st)
             std::deque<uint32_t> &Q = P->pending[klass];
             for (uint32_t a = 0; a < take[klass]; ++a) {
                 const uint32_t ti = Q.front();
+                {
+                    const uint32_t ix_id = P->tickets[ti].index->id;
+                    const uint32_t d = n_distinct + (P->index_seen[ix_id] ? 0u : 1u);
+                    if (d + ((uint32_t)P->newq.size() + 1) / P->coarse_rows > TRI_MAX_COARSE_GROUPS) break;
+                    P->index_seen[ix_id] = 1;
+                    n_distinct = d;
+                }
                 Q.pop_front();
                 const uint32_t slot = P->free_slots.back();
                 P->free_slots.pop_back();
@@ -939,6 +1022,8 @@ extern "C" int search_step(tri_pool *P, tri_step_stats *st)
     std::stable_sort(P->newq.begin(), P->newq.end(), [&](uint32_t a, uint32_t b) {
         return P->tickets[a].index->id < P->tickets[b].index->id;
     });
+    TriStepHdr *hdr_h = (TriStepHdr *)R.up_host;
+    TriNewDesc *desc_h = (TriNewDesc *)(R.up_host + sizeof(TriStepHdr));
     const size_t desc_bytes = round_up_sz((size_t)n_new * sizeof(TriNewDesc), 256);
 
     // ---- plan: every running slot, higher class first, then admission order
@@ -959,7 +1044,7 @@ extern "C" int search_step(tri_pool *P, tri_step_stats *st)
         ro.resize(w);
         P->run_seq[klass].resize(w);
     }
-    TriPlanEntry *plan_h = (TriPlanEntry *)(R.up_host + desc_bytes);
+    TriPlanEntry *plan_h = (TriPlanEntry *)(R.up_host + sizeof(TriStepHdr) + desc_bytes);
     uint32_t n_plan = 0, n_items = 0, n_retire = 0;
     uint64_t score_used = 0;
     R.retire.clear();
@@ -992,7 +1077,7 @@ extern "C" int search_step(tri_pool *P, tri_step_stats *st)
         return TRI_OK;
     }
 
-    // ---- upload block: [descs][plan][rows]
+    // ---- upload block: [header][admission records][plan]; behind it, on the device only, the row area
     const size_t plan_bytes = round_up_sz((size_t)n_plan * sizeof(TriPlanEntry), 256);
     uint32_t row_off = 0;
     for (uint32_t i = 0; i < n_new; ++i) {
@@ -1000,40 +1085,38 @@ extern "C" int search_step(tri_pool *P, tri_step_stats *st)
         desc_h[i] = TriNewDesc{t.slot, t.index->id, t.metric, t.k, t.nprobe, row_off, (uint64_t)(uintptr_t)t.dev_vec};
         row_off += t.index->row_bytes;     // (its place in the device row area; the kernel fetches the vector itself)
     }
-    const size_t up_bytes = desc_bytes + plan_bytes;   // (query rows are read by the admit kernel from where they lie)
-    hipStream_t s = P->stream;
-    const bool prof = (cfg.flags & TRI_FLAG_PROFILE) != 0;
-    const bool prof_scan = !prof && (cfg.flags & TRI_FLAG_PROFILE_SCAN) != 0;
-    HIP_TRY(tri_launch_pull_block(s, P->ws.upload, R.up_dev, up_bytes));
-    const TriNewDesc *desc_d = (const TriNewDesc *)P->ws.upload;
-    const TriPlanEntry *plan_d = (const TriPlanEntry *)(P->ws.upload + desc_bytes);
-    uint8_t *rows_d = P->ws.upload + desc_bytes + plan_bytes;
-
-    if (prof) HIP_TRY(hipEventRecord(R.ev[0], s));
-    HIP_TRY(tri_launch_admit(P->ctx, P->ws, desc_d, rows_d, n_new));
-    if (prof) HIP_TRY(hipEventRecord(R.ev[1], s));
-    // ---- coarse ranking of the admitted queries, index by index
-    for (uint32_t a = 0; a < n_new;) {
-        tri_index *ix = P->tickets[P->newq[a]].index;
-        uint32_t b = a;
-        while (b < n_new && P->tickets[P->newq[b]].index == ix) ++b;
-        const uint32_t ldc = round_up(ix->p.nlist, 32);
-        for (uint32_t c = a; c < b; c += P->coarse_rows) {
-            const uint32_t m = std::min(P->coarse_rows, b - c);
-            HIP_TRY(tri_launch_coarse_gemm(s, (int)ix->p.dtype, rows_d + desc_h[c].row_off, ix->row_bytes, m,
-                                           ix->dev.centroids, ix->dev.cnorm, ix->p.nlist, ix->row_bytes,
-                                           &desc_d[c].metric, (uint32_t)(sizeof(TriNewDesc) / 4), 0u, P->ws.coarse_scores, ldc));
-            HIP_TRY(tri_launch_coarse_select(P->ctx, P->ws, desc_d, c, m, ix->p.nlist, ldc));
-        }
-        a = b;
-    }
-    if (prof) HIP_TRY(hipEventRecord(R.ev[2], s));
+    const size_t up_bytes = sizeof(TriStepHdr) + desc_bytes + plan_bytes;
     // chunk length floor of this step: with fewer tiles than a few per wavefront, cut the lists finer.
     // Tiles are estimated from the item count: below one item per attached list every item is a tile of
     // its own, above it a list's items share tiles of TRI_QT queries.
     const uint64_t per_list = P->n_order ? (n_items + P->n_order - 1) / P->n_order : 1;
     const uint64_t tiles_est = n_items <= P->n_order ? n_items : (uint64_t)P->n_order * ((per_list + TRI_QT - 1) / TRI_QT);
-    const uint32_t min_chunk = tiles_est < 16u * P->ctx.n_cu ? 128u : 1024u;
+    hdr_h->n16 = (uint32_t)(up_bytes / 16);
+    hdr_h->n_new = n_new;
+    hdr_h->n_plan = n_plan;
+    hdr_h->n_items = n_items;
+    hdr_h->min_chunk = tiles_est < 16u * P->ctx.n_cu ? 128u : 1024u;
+    hdr_h->desc_off = (uint32_t)sizeof(TriStepHdr);
+    hdr_h->plan_off = (uint32_t)(sizeof(TriStepHdr) + desc_bytes);
+    hdr_h->rows_off = (uint32_t)up_bytes;
+    // coarse ranking of the admitted queries: groups of one index and at most coarse_rows rows
+    uint32_t n_groups = 0;
+    for (uint32_t a = 0; a < n_new;) {
+        tri_index *ix = P->tickets[P->newq[a]].index;
+        uint32_t b = a;
+        while (b < n_new && P->tickets[P->newq[b]].index == ix) ++b;
+        for (uint32_t c = a; c < b; c += P->coarse_rows) {
+            if (n_groups == TRI_MAX_COARSE_GROUPS) return fail(TRI_EINVAL, "internal: more coarse groups than the step header holds");
+            hdr_h->group[n_groups++] = TriCoarseGroup{c, std::min(P->coarse_rows, b - c), ix->id, desc_h[c].row_off};
+        }
+        a = b;
+    }
+    hdr_h->n_groups = n_groups;
+
+    hipStream_t s = P->stream;
+    const bool prof = (cfg.flags & TRI_FLAG_PROFILE) != 0;
+    const bool prof_scan = !prof && (cfg.flags & TRI_FLAG_PROFILE_SCAN) != 0;
+    const bool replay = (cfg.flags & TRI_FLAG_GRAPH) && !prof && !prof_scan;
     // Everything the host wants back lands in this step's pinned host block, written by the kernels
     // themselves (the stores cross the bus while the kernels work on): no copy after the step.
     // (A result copy on a second stream was tried instead; it ran beside the next step's scan and slowed
@@ -1041,17 +1124,38 @@ extern "C" int search_step(tri_pool *P, tri_step_stats *st)
     TriDevWs W = P->ws;
     W.res_block = (uint32_t *)R.down_dev;
     W.res_probes = (uint32_t *)(R.down_dev + P->down_probe_off);
-    W.step_host = prof || prof_scan ? (TriStepDev *)(R.down_dev + P->down_step_off) : nullptr;
-    HIP_TRY(tri_launch_pack(P->ctx, W, plan_d, n_plan, n_items, P->total_lists, P->n_order, min_chunk));
-    if (prof) HIP_TRY(hipEventRecord(R.ev[3], s));
-    // thresholds: score a sample of every probed list, k-th best of each slot's sample
-    if (n_items) HIP_TRY(tri_launch_scan(P->ctx, P->ws, P->attached_row_bytes, P->scan_class_mask, true));
-    if (n_items) HIP_TRY(tri_launch_threshold(P->ctx, P->ws, plan_d, n_plan));
-    if (prof || (prof_scan && n_items)) HIP_TRY(hipEventRecord(R.ev[4], s));
-    if (n_items) HIP_TRY(tri_launch_scan(P->ctx, P->ws, P->attached_row_bytes, P->scan_class_mask, false));
-    if (prof || (prof_scan && n_items)) HIP_TRY(hipEventRecord(R.ev[5], s));
-    HIP_TRY(tri_launch_merge(P->ctx, W, plan_d, n_plan, (cfg.flags & TRI_FLAG_KEEP_PROBES) != 0, min_chunk));
-    if (prof) HIP_TRY(hipEventRecord(R.ev[6], s));
+    const bool keep_probes = (cfg.flags & TRI_FLAG_KEEP_PROBES) != 0;
+    if (replay) {
+        // Sec. 3.2: the step's launch sequence, recorded once at its fixed, largest shape, is replayed; what
+        // this step holds stands in the header the first kernel pulls.
+        if (!R.graph_exec) {
+            rc = record_step(P, R, W, keep_probes);
+            if (rc) return rc;
+        }
+        HIP_TRY(hipGraphLaunch(R.graph_exec, s));
+    } else {
+        W.step_host = prof || prof_scan ? (TriStepDev *)(R.down_dev + P->down_step_off) : nullptr;
+        HIP_TRY(tri_launch_pull_block(s, P->ws.upload, R.up_dev, up_bytes));
+        if (prof) HIP_TRY(hipEventRecord(R.ev[0], s));
+        HIP_TRY(tri_launch_admit(P->ctx, P->ws, n_new));
+        if (prof) HIP_TRY(hipEventRecord(R.ev[1], s));
+        for (uint32_t g = 0; g < n_groups; ++g) {
+            const tri_index *ix = P->indexes[hdr_h->group[g].index];
+            HIP_TRY(tri_launch_coarse_gemm_step(P->ctx, P->ws, (int)ix->p.dtype, g, hdr_h->group[g].m, ix->p.nlist));
+            HIP_TRY(tri_launch_coarse_select(P->ctx, P->ws, g, hdr_h->group[g].m));
+        }
+        if (prof) HIP_TRY(hipEventRecord(R.ev[2], s));
+        HIP_TRY(tri_launch_pack(P->ctx, W, n_items, P->total_lists, P->n_order));
+        if (prof) HIP_TRY(hipEventRecord(R.ev[3], s));
+        // thresholds: score a sample of every probed list, k-th best of each slot's sample
+        if (n_items) HIP_TRY(tri_launch_scan(P->ctx, P->ws, P->attached_row_bytes, P->scan_class_mask, true));
+        if (n_items) HIP_TRY(tri_launch_threshold(P->ctx, P->ws, n_plan));
+        if (prof || (prof_scan && n_items)) HIP_TRY(hipEventRecord(R.ev[4], s));
+        if (n_items) HIP_TRY(tri_launch_scan(P->ctx, P->ws, P->attached_row_bytes, P->scan_class_mask, false));
+        if (prof || (prof_scan && n_items)) HIP_TRY(hipEventRecord(R.ev[5], s));
+        HIP_TRY(tri_launch_merge(P->ctx, W, n_plan, keep_probes));
+        if (prof) HIP_TRY(hipEventRecord(R.ev[6], s));
+    }
     HIP_TRY(hipEventRecord(R.done, s));
     R.in_use = true;
     R.enqueue_ns = now_ns();

@@ -52,6 +52,29 @@ struct TriPlanEntry {
     uint32_t pad_;
 };
 
+// What a step's kernels need to know about it, at the head of the step's upload block.  Every kernel of
+// the step reads its counts from here, never from a launch argument, so that the launch sequence of a
+// step is the same whatever the step holds (paper Sec. 3.2: a step of fixed shape that can be captured
+// once and replayed); grids may be larger than the step needs, the surplus workgroups leave at once.
+#define TRI_MAX_COARSE_GROUPS 60
+struct TriCoarseGroup {      // newly admitted queries [first_new, first_new + m) target one index
+    uint32_t first_new, m, index, row_off;   // row_off: byte offset of the group's first padded row in the row area
+};
+struct TriStepHdr {
+    uint32_t n16;            // 16-byte pieces of the upload block (this header, admission records, plan)
+    uint32_t n_new;          // admission records
+    uint32_t n_plan;         // plan entries (running slots that take part in this step)
+    uint32_t n_items;        // work items of the step
+    uint32_t min_chunk;      // chunk length floor of the step (tri_chunk_vecs)
+    uint32_t desc_off;       // byte offsets inside the upload block
+    uint32_t plan_off;
+    uint32_t rows_off;       // row area (filled on the device by the admit kernel)
+    uint32_t n_groups;
+    uint32_t pad_[7];
+    TriCoarseGroup group[TRI_MAX_COARSE_GROUPS];
+};
+static_assert(sizeof(TriStepHdr) == 1024, "header is 1024 bytes");
+
 // One scan tile: up to TRI_QT queries against one chunk (all of it, for short lists) of one inverted
 // list.  Self-contained: the scan kernels read nothing else about the list.  Two kinds share the layout:
 //  * main tiles: every vector of the chunk is scored, the scores that pass the query's threshold are
@@ -156,25 +179,31 @@ struct TriLaunchCtx {
 };
 
 // ---- launchers (each returns hipGetLastError() of its launches) -----------------------------
+// The kernels of a step read what the step holds from the TriStepHdr at the head of ws.upload; the
+// grid_* arguments only size the launches: at least what the step needs (its exact counts, or the
+// pool's maxima when the sequence is recorded once for replay).
 hipError_t tri_launch_fill_u32(hipStream_t s, uint32_t *p, uint32_t v, size_t n);
-hipError_t tri_launch_pull_block(hipStream_t s, void *dst_dev, const void *src_host_as_device, size_t bytes);
-hipError_t tri_launch_admit(const TriLaunchCtx &c, const TriDevWs &ws, const TriNewDesc *desc_dev,
-                            uint8_t *rows_dev, uint32_t n_new);
+hipError_t tri_launch_pull_block(hipStream_t s, void *dst_dev, const void *src_host_as_device, size_t grid_bytes);
+hipError_t tri_launch_admit(const TriLaunchCtx &c, const TriDevWs &ws, uint32_t grid_new);
 // scores[m][ldc] for m rows (pitch a_pitch_bytes) against n rows of b (pitch row_bytes); the metric
 // is per row (row_metric[m * metric_stride_u32]) or, with row_metric == NULL, fixed_metric.
 hipError_t tri_launch_coarse_gemm(hipStream_t s, int dtype, const void *a_rows, uint32_t a_pitch_bytes,
                                   uint32_t m, const void *b_rows, const float *b_norm, uint32_t n,
                                   uint32_t row_bytes, const uint32_t *row_metric, uint32_t metric_stride_u32,
                                   uint32_t fixed_metric, float *scores, uint32_t ldc);
-hipError_t tri_launch_coarse_select(const TriLaunchCtx &c, const TriDevWs &ws, const TriNewDesc *desc_dev,
-                                    uint32_t first_new, uint32_t m, uint32_t nlist, uint32_t ldc);
-hipError_t tri_launch_pack(const TriLaunchCtx &c, const TriDevWs &ws, const TriPlanEntry *plan_dev,
-                           uint32_t n_plan, uint32_t n_items, uint32_t total_lists, uint32_t n_order,
-                           uint32_t min_chunk);
+// the same for group `group` of the step's header (rows of the step's row area against the group's index),
+// into ws.coarse_scores with a row pitch of nlist rounded up to 32; dtype = the kernel variant to launch
+hipError_t tri_launch_coarse_gemm_step(const TriLaunchCtx &c, const TriDevWs &ws, int dtype, uint32_t group,
+                                       uint32_t grid_m, uint32_t grid_n);
+hipError_t tri_launch_coarse_select(const TriLaunchCtx &c, const TriDevWs &ws, uint32_t group, uint32_t grid_m);
+hipError_t tri_launch_pack(const TriLaunchCtx &c, const TriDevWs &ws, uint32_t grid_items, uint32_t total_lists,
+                           uint32_t n_order);
 hipError_t tri_launch_scan(const TriLaunchCtx &c, const TriDevWs &ws, uint32_t max_row_bytes, uint32_t class_mask,
                            bool sample);
-hipError_t tri_launch_threshold(const TriLaunchCtx &c, const TriDevWs &ws, const TriPlanEntry *plan_dev,
-                                uint32_t n_plan);
+hipError_t tri_launch_threshold(const TriLaunchCtx &c, const TriDevWs &ws, uint32_t grid_plan);
+// one-time set-up the launchers above would otherwise do at their first launch (LDS limits)
+hipError_t tri_scan_prepare(uint32_t max_row_bytes, uint32_t class_mask);
+hipError_t tri_coarse_prepare();
 #define TRI_TILES_PER_ITEM 4   // tile capacity = 4 W: a list is cut into at most 4 chunks
 
 // Chunking of a list for the scan: at most TRI_TILES_PER_ITEM chunks of equal length (a multiple of 32
@@ -194,8 +223,7 @@ __host__ __device__ inline uint32_t tri_scan_class(uint32_t dtype, uint32_t row_
     const bool special = row_bytes == 512 || row_bytes == 1024 || row_bytes == 1536 || row_bytes == 2048;
     return dtype * 5 + (special ? row_bytes / 512 : 0);
 }
-hipError_t tri_launch_merge(const TriLaunchCtx &c, const TriDevWs &ws, const TriPlanEntry *plan_dev,
-                            uint32_t n_plan, bool keep_probes, uint32_t min_chunk);
+hipError_t tri_launch_merge(const TriLaunchCtx &c, const TriDevWs &ws, uint32_t grid_plan, bool keep_probes);
 
 // ---- index construction helpers ------------------------------------------------------------
 hipError_t tri_build_pad_rows(hipStream_t s, int dtype, const void *src, uint32_t dim, uint64_t src_pitch_elems,

@@ -22,12 +22,13 @@ def default_pool(tri, **over):
     return tri.Pool(**cfg)
 
 
-def run_all(tri, pool, queries, max_steps=100000, submit_chunks=None):
+def run_all(tri, pool, queries, max_steps=100000, submit_chunks=None, between_steps=None):
     """Submit `queries` (QUERY_DTYPE array), step until everything is finished, poll.
 
     submit_chunks: None = submit everything first; else a list of chunk sizes, one chunk submitted
     before each step (the rest after the list is exhausted goes in with the last chunk) -- queries
-    then arrive mid-stream.  Returns (ids [n, kmax], dist [n, kmax], n_out [n], probes list, stats list).
+    then arrive mid-stream.  between_steps: called after every search_step (e.g. to synchronise or to run
+    other GPU work).  Returns (ids [n, kmax], dist [n, kmax], n_out [n], probes list, stats list).
     """
     n = queries.shape[0]
     kmax = int(queries["k"].max()) if n else 1
@@ -50,6 +51,8 @@ def run_all(tri, pool, queries, max_steps=100000, submit_chunks=None):
             pos += take
         st = tri.search_step(pool.handle)
         stats.append((st.admitted, st.retired, st.running, st.items))
+        if between_steps:
+            between_steps()
         steps += 1
         assert steps < max_steps, "search_step loop did not drain"
         if pos >= n and st.running == 0 and st.pending_high == 0 and st.pending_low == 0 and st.items == 0:

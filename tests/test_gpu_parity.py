@@ -172,6 +172,10 @@ def test_scheduling_does_not_change_results():
         "7 slots": dict(pool=dict(slots=7, max_outstanding=256), chunks=None),
         "mid-stream": dict(pool=dict(lists_per_query_step=2, slots=40), chunks=[1, 5, 20, 3, 50, 1, 1]),
         "tiny score buffer": dict(pool=dict(score_capacity=2048), chunks=None),
+        "recorded step": dict(pool=dict(flags=tri.TRI_FLAG_KEEP_PROBES | tri.TRI_FLAG_GRAPH), chunks=None),
+        "recorded step, mid-stream": dict(pool=dict(lists_per_query_step=2, slots=40,
+                                                    flags=tri.TRI_FLAG_KEEP_PROBES | tri.TRI_FLAG_GRAPH),
+                                          chunks=[1, 5, 20, 3, 50, 1, 1]),
     }
     ref = None
     for name, v in variants.items():
@@ -356,6 +360,63 @@ def test_every_row_length_class_and_long_lists(dtype, dim):
             ids2, dist2, n2, probes2, stats2 = harness.run_all(tri, pool2, q2)
             assert np.array_equal(ids, ids2) and np.array_equal(n_out, n2)
             assert np.array_equal(dist.view(np.uint32), dist2.view(np.uint32))
+
+
+def test_recorded_step_replays_match_kernel_by_kernel_launches():
+    """TRI_FLAG_GRAPH: the step recorded once as a HIP graph and replayed gives, replay after replay and
+    with other GPU work and synchronisations in between, bit for bit what kernel-by-kernel launches
+    give -- over two indexes of different storage types, mid-stream arrivals and slot reuse -- and
+    survives a change of the set of attached indexes (the recording is made again)."""
+    import torch
+    tri = harness.lib()
+    cfg_a = workloads.CONFIGS[2].scaled(n_base=20_000, n_components=64, nlist=64, n_queries=60)
+    cfg_b = workloads.CONFIGS[0].scaled(n_base=5_000, n_components=16, nlist=32, n_queries=60, dim=40)
+    base_a_t, base_a, queries_a, rows_a = _f16_setup(tri, cfg_a)
+    base_b, queries_b, rows_b = workloads.make_config01(cfg_b)
+    order = np.random.default_rng(9).permutation(120)
+    inv = np.argsort(order)
+    k_a = np.random.default_rng(3).integers(1, 100, size=60).astype(np.uint32)
+    results = {}
+    scratch = torch.zeros(1 << 20, device="cuda")
+
+    def busy():                        # the program's own work between two replays
+        scratch.add_(1.0)
+        torch.cuda.synchronize()
+
+    for name, flags in [("eager", tri.TRI_FLAG_KEEP_PROBES), ("graph", tri.TRI_FLAG_KEEP_PROBES | tri.TRI_FLAG_GRAPH)]:
+        _say(f"recorded step: {name}")
+        with harness.default_pool(tri, slots=24, max_dim=768, max_outstanding=512, lists_per_query_step=4,
+                                  flags=flags) as pool:
+            ia = pool.build_index(base_a_t, cfg_a.dim, cfg_a.nlist, tri.TRI_F16, tri.TRI_IP, 5,
+                                  centroids=base_a[rows_a].astype(np.float32))
+            qa = tri.make_queries(ia, queries_a, k_a, 16, tri.TRI_IP, tri.TRI_CLASS_LOW)
+            if name == "graph":        # steps recorded with one index attached ...
+                ids, dist, n_out, probes, _ = harness.run_all(tri, pool, qa, between_steps=busy)
+                results["graph, one index"] = (ids, dist, n_out, probes)
+            ib = pool.build_index(base_b, cfg_b.dim, cfg_b.nlist, tri.TRI_F32, tri.TRI_L2, 5, centroids=base_b[rows_b])
+            qb = tri.make_queries(ib, queries_b, 5, 8, tri.TRI_L2, tri.TRI_CLASS_HIGH)
+            mixed = np.ascontiguousarray(np.concatenate([qa, qb])[order])
+            runs = []
+            for rep in range(3 if name == "graph" else 1):      # ... and again with two
+                ids, dist, n_out, probes, stats = harness.run_all(tri, pool, mixed, submit_chunks=[10, 30, 5],
+                                                                  between_steps=busy if rep != 1 else None)
+                runs.append((ids[inv], dist[inv], n_out[inv], [probes[i] for i in inv]))
+                _say(f"  run {rep}: {len(stats)} steps")
+            results[name] = runs
+            if name == "eager":
+                oa, ob = harness.oracle_index(tri, ia, base_a), harness.oracle_index(tri, ib, base_b)
+                ids, dist, n_out, probes = runs[0]
+                harness.compare_with_oracle(oa, base_a, queries_a, k_a, 16, 1, ids[:60], dist[:60], n_out[:60], probes[:60])
+                harness.compare_with_oracle(ob, base_b, queries_b, 5, 8, 0, ids[60:], dist[60:], n_out[60:], probes[60:])
+    ref = results["eager"][0]
+    for rep, got in enumerate(results["graph"]):
+        assert np.array_equal(got[0], ref[0]), f"replayed run {rep}: ids"
+        assert np.array_equal(got[1].view(np.uint32), ref[1].view(np.uint32)), f"replayed run {rep}: scores"
+        assert np.array_equal(got[2], ref[2]), f"replayed run {rep}: counts"
+        assert all(np.array_equal(a, b) for a, b in zip(got[3], ref[3])), f"replayed run {rep}: probe lists"
+    one = results["graph, one index"]
+    assert np.array_equal(one[0][:, :1], ref[0][:60, :1])       # (same queries, same index: same best neighbour)
+    assert float(scratch[0]) > 0
 
 
 def test_more_probed_lists_than_cached_segments():
