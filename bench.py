@@ -97,7 +97,7 @@ def main():
     pool = tri.Pool(slots=Q, items_per_step=items, lists_per_query_step=0, kmax=max(kmax, 16),
                     nprobe_max=int(nprobe.max()), max_indexes=1, max_total_lists=cfg.nlist, max_nlist=cfg.nlist,
                     max_dim=cfg.dim, max_outstanding=Q * 8, coarse_rows=Q, flags=tri.TRI_FLAG_PROFILE_SCAN,
-                    score_capacity=(1 << 31))
+                    score_capacity=(1 << 31), own_stream=True)
     log("building the index (untimed)")
     t_b = time.time()
     init = base_t[torch.from_numpy(rows).cuda()].float().cpu().numpy()
@@ -186,7 +186,16 @@ def main():
     tri.tri_pool_kernel_times(pool.handle, reset=True)
     timed(10)
     ks = tri.tri_pool_kernel_times(pool.handle)
+    # the same loop with the step replayed from its recording (Sec. 3.2), then kernel by kernel, both unprofiled
+    tri.tri_pool_set_profiling(pool.handle, 0)
+    tri.tri_pool_set_replay(pool.handle, True)
+    timed(5)
+    replay_ms = timed(max(10, args.steps // 4)) * 1e3 / max(10, args.steps // 4)
+    tri.tri_pool_set_replay(pool.handle, False)
+    timed(5)
+    eager_ms = timed(max(10, args.steps // 4)) * 1e3 / max(10, args.steps // 4)
     tri.tri_pool_set_profiling(pool.handle, tri.TRI_FLAG_PROFILE_SCAN)
+    log(f"step replayed from its recording: {replay_ms:.3f} ms/step; kernel by kernel, no events: {eager_ms:.3f} ms/step")
     scan_ms = kt.scan_ms / max(kt.scan_launches, 1)
     unique_b = kt.scan_unique_bytes / max(kt.scan_launches, 1)
     tile_b = kt.scan_vector_bytes / max(kt.scan_launches, 1)
@@ -255,6 +264,8 @@ def main():
                                "pack": round(ks.pack_ms / ks.steps, 4), "sample": round(ks.sample_ms / ks.steps, 4),
                                "scan": round(ks.scan_ms / ks.steps, 4), "select": round(ks.select_ms / ks.steps, 4),
                                "note": "10 more steps with every stage bracketed by events"},
+        "step_launch": {"replayed_graph_ms_per_step": round(replay_ms, 4), "kernel_by_kernel_ms_per_step": round(eager_ms, 4),
+                        "note": "same loop, unprofiled, after the timed region (which launches kernel by kernel with two events around the scan)"},
         "cpu_baseline": cpu,
         "wall_s_total": round(time.time() - t_start, 1),
     }
@@ -276,7 +287,7 @@ def stream_bench(args, tri, workloads, torch):
     pool = tri.Pool(slots=slots, items_per_step=slots * p, lists_per_query_step=p, kmax=128, nprobe_max=32,
                     max_indexes=2, max_total_lists=rag_cfg.nlist + cache_cfg.nlist, max_nlist=rag_cfg.nlist,
                     max_dim=768, max_outstanding=n, coarse_rows=0, flags=tri.TRI_FLAG_PROFILE,
-                    score_capacity=256 << 20)
+                    score_capacity=256 << 20, own_stream=True)
     log("building the two indexes (untimed)")
     init_r = w["rag_base"][torch.from_numpy(w["rag_rows"]).cuda()].float().cpu().numpy()
     init_c = w["cache_base"][torch.from_numpy(w["cache_rows"]).cuda()].float().cpu().numpy()
@@ -330,6 +341,18 @@ def stream_bench(args, tri, workloads, torch):
     runs.append(run(burst, "burst, reserved share 0.3, least slack first, 20 ms budget on cache lookups",
                     qq=q_ddl, high_share=0.3, order_high=tri.TRI_ORDER_SLACK)[0])
     tri.search_set_policy(pool.handle)
+    # launch overhead of a step (Sec. 3.2: the captured fixed-shape step): the same streams unprofiled,
+    # kernel by kernel and replayed from the recording
+    tri.tri_pool_set_profiling(pool.handle, 0)
+    low = workloads.poisson_arrivals(n, 1.0e5, 4003)
+    for replay in (False, True):
+        tri.tri_pool_set_replay(pool.handle, replay)
+        how = "replayed recording" if replay else "kernel by kernel"
+        run(burst, f"warmup ({how})")
+        runs.append(run(burst, f"closed loop, no profiling events, {how}")[0])
+        runs.append(run(low, f"Poisson arrivals at 100,000 / s, no profiling events, {how}")[0])
+    tri.tri_pool_set_replay(pool.handle, False)
+    tri.tri_pool_set_profiling(pool.handle, tri.TRI_FLAG_PROFILE)
 
     cpu = None
     n_cpu = args.cpu_sample if args.cpu_sample >= 0 else 512

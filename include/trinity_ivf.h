@@ -55,11 +55,12 @@ enum { TRI_FLAG_PROFILE = 1u,             /* bracket every stage of a step with 
        TRI_FLAG_PROFILE_SCAN = 4u,        /* bracket only the list scan (two events): scan_ms and the scan_* counters
                                              of tri_pool_kernel_times are filled, the other stage times stay zero    */
        TRI_FLAG_GRAPH = 8u };             /* Sec. 3.2 (fixed-shape step captured once, replayed): the launch sequence
-                                             of a step is recorded as a HIP graph at the pool's largest shape (once per
-                                             step in flight and set of attached indexes) and search_step replays it; what
-                                             a step holds travels in its upload block.  Needs hip_stream != the default
-                                             stream (TRI_EHIP from the first search_step otherwise).  Results are
-                                             identical to those without the flag.  Steps that are profiled
+                                             of a step is recorded as a HIP graph at three captured sizes (1/16, 1/4 and
+                                             all of slots and items_per_step; once per size, step in flight and set of
+                                             attached indexes); search_step replays the smallest that holds the step, the
+                                             surplus workgroups are masked by the counts in the step's upload block.
+                                             Needs hip_stream != the default stream (TRI_EINVAL from tri_pool_create).
+                                             Results are identical to those without the flag.  Steps that are profiled
                                              (TRI_FLAG_PROFILE*) are launched kernel by kernel.                        */
 
 /* Limits of this implementation (checked, TRI_EINVAL beyond them). */
@@ -310,6 +311,10 @@ int tri_pool_kernel_times(tri_pool *pool, tri_kernel_times *out /*[host] out*/, 
 /* Switch the profiling of the steps enqueued from now on: flags = 0, TRI_FLAG_PROFILE or
  * TRI_FLAG_PROFILE_SCAN (the other flags of the pool are fixed at creation). */
 int tri_pool_set_profiling(tri_pool *pool, uint32_t flags);
+/* Sec. 3.2 (captured fixed-shape step): switch TRI_FLAG_GRAPH for the steps enqueued from now on: on != 0 =
+ * replay the recorded launch sequence, 0 = launch kernel by kernel.  TRI_EINVAL for a pool on the default
+ * stream (a step cannot be recorded there). */
+int tri_pool_set_replay(tri_pool *pool, int on);
 
 const char *tri_last_error(void);
 const char *tri_version(void);

@@ -88,7 +88,7 @@ EXPORTS = ["tri_pool_workspace_bytes", "tri_pool_create", "tri_pool_destroy", "i
            "ivf_export", "ivf_info", "ivf_destroy", "search_submit", "search_submit_batch", "search_submit_batch_dev",
            "search_step", "search_poll", "search_poll_batch", "search_probes", "search_cancel", "search_sync",
            "search_run_stream", "search_set_policy", "search_get_policy", "tri_policy_split", "tri_policy_slack_order",
-           "tri_pool_kernel_times", "tri_pool_set_profiling", "tri_last_error", "tri_version"]
+           "tri_pool_kernel_times", "tri_pool_set_profiling", "tri_pool_set_replay", "tri_last_error", "tri_version"]
 
 
 def _load():
@@ -125,6 +125,7 @@ def _load():
     lib.tri_policy_slack_order.argtypes = [u32, vp, vp, ctypes.c_int64, ctypes.c_int64, u32, vp]
     lib.tri_pool_kernel_times.argtypes = [vp, P(tri_kernel_times), ctypes.c_int]
     lib.tri_pool_set_profiling.argtypes = [vp, u32]
+    lib.tri_pool_set_replay.argtypes = [vp, ctypes.c_int]
     lib.tri_last_error.restype = ctypes.c_char_p
     lib.tri_version.restype = ctypes.c_char_p
     for name in EXPORTS:
@@ -174,6 +175,10 @@ def tri_pool_destroy(pool: int) -> None:
 
 def tri_pool_set_profiling(pool: int, flags: int) -> None:
     _check(_lib.tri_pool_set_profiling(ctypes.c_void_p(pool), flags), "tri_pool_set_profiling")
+
+
+def tri_pool_set_replay(pool: int, on: bool) -> None:
+    _check(_lib.tri_pool_set_replay(ctypes.c_void_p(pool), 1 if on else 0), "tri_pool_set_replay")
 
 
 def tri_pool_kernel_times(pool: int, reset: bool = False) -> tri_kernel_times:
@@ -386,9 +391,10 @@ class Pool:
         import torch
         if not torch.cuda.is_available():
             raise RuntimeError("no GPU: the search path has no CPU fallback")
-        self.cfg = tri_pool_cfg(**cfg_fields)
         # (a step can only be recorded for replay on a stream of its own, never on the default stream)
-        self._stream = torch.cuda.Stream() if self.cfg.flags & TRI_FLAG_GRAPH else torch.cuda.current_stream()
+        own_stream = bool(cfg_fields.pop("own_stream", False))
+        self.cfg = tri_pool_cfg(**cfg_fields)
+        self._stream = torch.cuda.Stream() if own_stream or self.cfg.flags & TRI_FLAG_GRAPH else torch.cuda.current_stream()
         self.cfg.hip_stream = self._stream.cuda_stream
         nbytes = tri_pool_workspace_bytes(self.cfg)
         self._ws = torch.empty(nbytes + 256, dtype=torch.uint8, device="cuda")

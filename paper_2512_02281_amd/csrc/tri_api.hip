@@ -42,6 +42,7 @@ int fail(int code, const char *fmt, ...)
 
 constexpr uint32_t RING = 4;          // steps that may be in flight before search_step waits
 constexpr uint32_t N_EV = 7;          // profile events per step
+constexpr uint32_t N_SHAPES = 3;      // captured sizes of a step: 1/16, 1/4 and all of the pool's slots and items
 
 inline int64_t now_ns()
 {
@@ -104,8 +105,10 @@ struct StepRec {
     std::vector<uint32_t> retire;     // ticket index per retire_idx
     uint32_t n_items = 0;
     bool had_scan = false;
-    hipGraph_t graph = nullptr;       // TRI_FLAG_GRAPH: the step's launch sequence with this entry's pinned blocks,
-    hipGraphExec_t graph_exec = nullptr;   // recorded once (per set of attached indexes) and replayed
+    // TRI_FLAG_GRAPH: the step's launch sequence with this entry's pinned blocks, recorded once per captured
+    // size (and set of attached indexes) and replayed
+    hipGraph_t graph[N_SHAPES] = {};
+    hipGraphExec_t graph_exec[N_SHAPES] = {};
 };
 
 }  // namespace
@@ -446,6 +449,8 @@ extern "C" int tri_pool_create(const tri_pool_cfg *cfg, void *dev_ws, size_t dev
     int rc = derive(cfg, &mrb, &cr, &ldc, &sc, &up);
     if (rc) return rc;
     if (!dev_ws || !out) return fail(TRI_EINVAL, "dev_ws / out is NULL");
+    if ((cfg->flags & TRI_FLAG_GRAPH) && !cfg->hip_stream)
+        return fail(TRI_EINVAL, "TRI_FLAG_GRAPH needs a stream of the pool's own: a step cannot be recorded on the default stream");
     if ((uintptr_t)dev_ws % 256) return fail(TRI_EINVAL, "dev_ws must be 256-byte aligned");
     const size_t need = carve(*cfg, mrb, cr, ldc, sc, up, nullptr, nullptr);
     if (dev_ws_bytes < need) return fail(TRI_ENOMEM, "dev_ws has %zu bytes, %zu needed", dev_ws_bytes, need);
@@ -891,45 +896,62 @@ void drop_graphs(tri_pool *P)
     (void)hipStreamSynchronize(P->stream);
     for (uint32_t i = 0; i < RING; ++i) {
         StepRec &R = P->ring[i];
-        if (R.graph_exec) (void)hipGraphExecDestroy(R.graph_exec);
-        if (R.graph) (void)hipGraphDestroy(R.graph);
-        R.graph_exec = nullptr;
-        R.graph = nullptr;
+        for (uint32_t b = 0; b < N_SHAPES; ++b) {
+            if (R.graph_exec[b]) (void)hipGraphExecDestroy(R.graph_exec[b]);
+            if (R.graph[b]) (void)hipGraphDestroy(R.graph[b]);
+            R.graph_exec[b] = nullptr;
+            R.graph[b] = nullptr;
+        }
     }
 }
 
-// Record the launch sequence of a step that uses ring entry R (its pinned upload and result blocks) at
-// the largest shape the pool allows: every slot admitted and running, W items, every coarse group,
-// every scan kernel variant the attached indexes need.  The kernels take what a step really holds from
-// its header, so one recording serves every later step until the set of attached indexes changes.
-int record_step(tri_pool *P, StepRec &R, const TriDevWs &W, bool keep_probes)
+// Captured sizes (Sec. 3.2: a step is rounded up to the next captured size, the surplus masked): shape b
+// holds up to slots >> shift and items >> shift, shift = 4, 2, 0.
+struct StepShape { uint32_t slots, items, groups; };
+
+StepShape step_shape(const tri_pool *P, uint32_t b)
 {
-    const tri_pool_cfg &cfg = P->cfg;
+    const uint32_t shift = 2u * (N_SHAPES - 1u - b);
+    uint32_t n_attached = 0;
+    for (const tri_index *ix : P->indexes) n_attached += ix != nullptr;
+    StepShape sh;
+    sh.slots = std::max(1u, P->cfg.slots >> shift);
+    sh.items = std::max(1u, P->cfg.items_per_step >> shift);
+    sh.groups = std::min<uint32_t>(TRI_MAX_COARSE_GROUPS, n_attached + sh.slots / P->coarse_rows);
+    return sh;
+}
+
+// Record the launch sequence of a step that uses ring entry R (its pinned upload and result blocks) at
+// captured size b: that many slots admitted and running, that many items, every coarse group they can
+// form, every scan kernel variant the attached indexes need.  The kernels take what a step really holds
+// from its header, so one recording serves every later step that fits, until the set of attached
+// indexes changes.
+int record_step(tri_pool *P, StepRec &R, const TriDevWs &W, bool keep_probes, uint32_t b)
+{
     hipStream_t s = P->stream;
-    uint32_t n_attached = 0, nlist_of[2] = {0, 0};
+    uint32_t nlist_of[2] = {0, 0};
     for (const tri_index *ix : P->indexes)
-        if (ix) {
-            ++n_attached;
-            nlist_of[ix->p.dtype == TRI_F16] = std::max(nlist_of[ix->p.dtype == TRI_F16], ix->p.nlist);
-        }
-    const uint32_t max_groups = std::min<uint32_t>(TRI_MAX_COARSE_GROUPS, n_attached + cfg.slots / P->coarse_rows);
+        if (ix) nlist_of[ix->p.dtype == TRI_F16] = std::max(nlist_of[ix->p.dtype == TRI_F16], ix->p.nlist);
+    const StepShape sh = step_shape(P, b);
+    const uint32_t group_rows = std::min(P->coarse_rows, sh.slots);
     hipError_t e = tri_scan_prepare(P->attached_row_bytes, P->scan_class_mask);
     if (e == hipSuccess) e = tri_coarse_prepare();
     if (e != hipSuccess) return fail(TRI_EHIP, "kernel set-up -> %s", hipGetErrorString(e));
     e = hipStreamBeginCapture(s, hipStreamCaptureModeThreadLocal);
     if (e != hipSuccess) return fail(TRI_EHIP, "hipStreamBeginCapture -> %s (a pool with TRI_FLAG_GRAPH needs a stream of its own, not the default stream)", hipGetErrorString(e));
-    e = tri_launch_pull_block(s, P->ws.upload, R.up_dev, P->upload_bytes - (size_t)cfg.slots * P->max_row_bytes);
-    if (e == hipSuccess) e = tri_launch_admit(P->ctx, P->ws, cfg.slots);
-    for (uint32_t g = 0; g < max_groups && e == hipSuccess; ++g) {
+    e = tri_launch_pull_block(s, P->ws.upload, R.up_dev,
+                              sizeof(TriStepHdr) + (size_t)sh.slots * (sizeof(TriNewDesc) + sizeof(TriPlanEntry)) + 512);
+    if (e == hipSuccess) e = tri_launch_admit(P->ctx, P->ws, sh.slots);
+    for (uint32_t g = 0; g < sh.groups && e == hipSuccess; ++g) {
         for (int dt = 0; dt < 2 && e == hipSuccess; ++dt)
-            if (nlist_of[dt]) e = tri_launch_coarse_gemm_step(P->ctx, P->ws, dt ? TRI_F16 : TRI_F32, g, P->coarse_rows, nlist_of[dt]);
-        if (e == hipSuccess) e = tri_launch_coarse_select(P->ctx, P->ws, g, P->coarse_rows);
+            if (nlist_of[dt]) e = tri_launch_coarse_gemm_step(P->ctx, P->ws, dt ? TRI_F16 : TRI_F32, g, group_rows, nlist_of[dt]);
+        if (e == hipSuccess) e = tri_launch_coarse_select(P->ctx, P->ws, g, group_rows);
     }
-    if (e == hipSuccess) e = tri_launch_pack(P->ctx, W, cfg.items_per_step, P->total_lists, P->n_order);
+    if (e == hipSuccess) e = tri_launch_pack(P->ctx, W, sh.items, P->total_lists, P->n_order);
     if (e == hipSuccess) e = tri_launch_scan(P->ctx, P->ws, P->attached_row_bytes, P->scan_class_mask, true);
-    if (e == hipSuccess) e = tri_launch_threshold(P->ctx, P->ws, cfg.slots);
+    if (e == hipSuccess) e = tri_launch_threshold(P->ctx, P->ws, sh.slots);
     if (e == hipSuccess) e = tri_launch_scan(P->ctx, P->ws, P->attached_row_bytes, P->scan_class_mask, false);
-    if (e == hipSuccess) e = tri_launch_merge(P->ctx, W, cfg.slots, keep_probes);
+    if (e == hipSuccess) e = tri_launch_merge(P->ctx, W, sh.slots, keep_probes);
     hipGraph_t g = nullptr;
     const hipError_t e2 = hipStreamEndCapture(s, &g);      // (always: a stream must not be left capturing)
     if (e != hipSuccess || e2 != hipSuccess) {
@@ -942,8 +964,8 @@ int record_step(tri_pool *P, StepRec &R, const TriDevWs &W, bool keep_probes)
         (void)hipGraphDestroy(g);
         return fail(TRI_EHIP, "hipGraphInstantiate -> %s", hipGetErrorString(e));
     }
-    R.graph = g;
-    R.graph_exec = x;
+    R.graph[b] = g;
+    R.graph_exec[b] = x;
     return TRI_OK;
 }
 
@@ -1128,11 +1150,16 @@ extern "C" int search_step(tri_pool *P, tri_step_stats *st)
     if (replay) {
         // Sec. 3.2: the step's launch sequence, recorded once at its fixed, largest shape, is replayed; what
         // this step holds stands in the header the first kernel pulls.
-        if (!R.graph_exec) {
-            rc = record_step(P, R, W, keep_probes);
+        uint32_t b = 0;                       // the smallest captured size this step fits
+        for (; b + 1 < N_SHAPES; ++b) {
+            const StepShape sh = step_shape(P, b);
+            if (n_new <= sh.slots && n_plan <= sh.slots && n_items <= sh.items && n_groups <= sh.groups) break;
+        }
+        if (!R.graph_exec[b]) {
+            rc = record_step(P, R, W, keep_probes, b);
             if (rc) return rc;
         }
-        HIP_TRY(hipGraphLaunch(R.graph_exec, s));
+        HIP_TRY(hipGraphLaunch(R.graph_exec[b], s));
     } else {
         W.step_host = prof || prof_scan ? (TriStepDev *)(R.down_dev + P->down_step_off) : nullptr;
         HIP_TRY(tri_launch_pull_block(s, P->ws.upload, R.up_dev, up_bytes));
@@ -1470,6 +1497,15 @@ extern "C" int tri_pool_set_profiling(tri_pool *P, uint32_t flags)
     if (flags & ~(uint32_t)(TRI_FLAG_PROFILE | TRI_FLAG_PROFILE_SCAN)) return fail(TRI_EINVAL, "only the profiling flags can be changed");
     std::lock_guard<std::mutex> lk(P->mu);
     P->cfg.flags = (P->cfg.flags & ~(uint32_t)(TRI_FLAG_PROFILE | TRI_FLAG_PROFILE_SCAN)) | flags;
+    return TRI_OK;
+}
+
+extern "C" int tri_pool_set_replay(tri_pool *P, int on)
+{
+    if (!P) return fail(TRI_EINVAL, "pool is NULL");
+    if (on && !P->stream) return fail(TRI_EINVAL, "a step cannot be recorded on the default stream: give the pool a stream of its own");
+    std::lock_guard<std::mutex> lk(P->mu);
+    P->cfg.flags = on ? (P->cfg.flags | TRI_FLAG_GRAPH) : (P->cfg.flags & ~(uint32_t)TRI_FLAG_GRAPH);
     return TRI_OK;
 }
 
