@@ -227,8 +227,8 @@ int search_sync(tri_pool *pool);
  * Scheduling policy at step boundaries (Sec. 3.3: two queues, a reserved share for the
  * latency-critical one, deadline-and-slack order inside it, short flush time-outs).  The high
  * class plays the part of the paper's prefill queue, the low class that of its decode queue.
- * May be changed between steps at any time (the paper's control loop does so every few hundred
- * milliseconds; that loop itself is not part of this library).
+ * May be changed between steps at any time; the paper's control loop, which does so every few
+ * hundred milliseconds, is search_set_feedback below.
  * ------------------------------------------------------------------------------------- */
 enum { TRI_ORDER_FIFO = 0, TRI_ORDER_SLACK = 1 };
 typedef struct {
@@ -259,6 +259,54 @@ int tri_policy_split(uint32_t free_slots, uint32_t n_high, uint32_t n_low, float
                      uint32_t *take_high /*[host] out*/, uint32_t *take_low /*[host] out*/);
 int tri_policy_slack_order(uint32_t n, const int64_t *deadline_ns /*[host] n*/, const uint32_t *steps_left /*[host] n*/,
                            int64_t now_ns, int64_t step_ns, uint32_t m, uint32_t *order /*[host] n out*/);
+
+/* ---------------------------------------------------------------------------------------
+ * The control loop of Sec. 3.3 (last part): every period it moves the reserved share r
+ * (tri_policy.high_share) and the high-class flush time-out tau_pre (flush_timeout_high_s) by
+ * what it is told about the serving system and what the pool measures itself:
+ *   u_kv          utilisation of the KV-cache link between the prefill and decode pools, in [0,1]
+ *                 (reported by the caller: it is measured outside this library);
+ *   decode_stall  fraction of decode time stalled waiting for retrieval, in [0,1] (reported);
+ *   wait_p95      95th percentile of the time high-class queries waited between submission and
+ *                 admission since the last period (measured by the pool).
+ * One period, in this order (the paper gives the directions, not the amounts: steps and factors
+ * are parameters):
+ *   1. u_kv < u_kv_target - u_kv_band: the high class must be served faster -> r += r_step, or,
+ *      with r already at r_max, tau_pre /= tau_factor;
+ *   2. wait_p95 > wait_p95_budget_s: tau_pre /= tau_factor;
+ *   3. if 1. did not apply and decode_stall > stall_target and decode_stall is higher than at
+ *      the last period: r -= r_step (the low class takes more of a batch);
+ *   4. if none of 1.-3. applied and wait_p95 <= wait_p95_budget_s / 2 (or nothing waited):
+ *      tau_pre *= tau_factor (relaxes towards tau_max_s).
+ * r stays in [r_min, r_max], tau_pre in [tau_min_s, tau_max_s].  A signal that is NaN is unknown
+ * and its rules do not apply.
+ * ------------------------------------------------------------------------------------- */
+typedef struct {
+    float r_min, r_max, r_step;          /* 0 <= r_min <= r_max <= 1, r_step > 0                          */
+    float tau_factor;                    /* > 1                                                           */
+    double tau_min_s, tau_max_s;         /* 0 <= tau_min_s <= tau_max_s                                   */
+    float u_kv_target, u_kv_band;        /* target utilisation of the KV link and the dead band below it  */
+    float stall_target;                  /* decode stall fraction that is tolerated                       */
+    float pad_;
+    double wait_p95_budget_s;            /* high-class wait (submission to admission) that is tolerated   */
+    double period_s;                     /* time between two adjustments (paper: a few hundred ms)        */
+} tri_feedback_cfg;
+typedef struct {
+    float u_kv, decode_stall, decode_stall_prev, pad_;
+    double wait_p95_s;
+} tri_feedback_signals;
+/* One period of the loop as a pure function (no GPU, no pool): policy is read and updated in place;
+ * *rules (may be NULL) receives a bit per rule 1..4 that applied (bit 0 = rule 1). */
+int tri_policy_feedback(const tri_feedback_cfg *cfg, const tri_feedback_signals *sig, tri_policy *policy /*in/out*/,
+                        uint32_t *rules /*[host] out or NULL*/);
+/* Run the loop inside the pool: search_step applies tri_policy_feedback to the policy in force whenever
+ * period_s has passed since the last time.  cfg = NULL switches it off.  The policy's high_share and
+ * flush_timeout_high_s are clamped into the configured ranges at once. */
+int search_set_feedback(tri_pool *pool, const tri_feedback_cfg *cfg /*[host] or NULL*/);
+/* Latest values of the signals measured outside the library (any thread); NaN = unknown. */
+int search_report_signals(tri_pool *pool, float u_kv, float decode_stall);
+/* Periods applied so far and the signals the last one saw (either output may be NULL). */
+int search_get_feedback(tri_pool *pool, uint64_t *periods /*[host] out*/, tri_feedback_signals *last /*[host] out*/);
 
 /* The serving loop of Sec. 3.2 (arrivals join at the next batch boundary, finished requests leave
  * at once) as one native call, for measuring a stream: query i is

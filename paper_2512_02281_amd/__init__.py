@@ -78,6 +78,18 @@ class tri_policy(ctypes.Structure):
                 ("flush_timeout_s", ctypes.c_double), ("flush_timeout_high_s", ctypes.c_double)]
 
 
+class tri_feedback_cfg(ctypes.Structure):
+    _fields_ = [("r_min", ctypes.c_float), ("r_max", ctypes.c_float), ("r_step", ctypes.c_float),
+                ("tau_factor", ctypes.c_float), ("tau_min_s", ctypes.c_double), ("tau_max_s", ctypes.c_double),
+                ("u_kv_target", ctypes.c_float), ("u_kv_band", ctypes.c_float), ("stall_target", ctypes.c_float),
+                ("pad_", ctypes.c_float), ("wait_p95_budget_s", ctypes.c_double), ("period_s", ctypes.c_double)]
+
+
+class tri_feedback_signals(ctypes.Structure):
+    _fields_ = [("u_kv", ctypes.c_float), ("decode_stall", ctypes.c_float), ("decode_stall_prev", ctypes.c_float),
+                ("pad_", ctypes.c_float), ("wait_p95_s", ctypes.c_double)]
+
+
 class tri_stream_stats(ctypes.Structure):
     _fields_ = [("wall_s", ctypes.c_double), ("steps", ctypes.c_uint64), ("items", ctypes.c_uint64),
                 ("capacity", ctypes.c_uint64), ("running", ctypes.c_uint64), ("max_pending", ctypes.c_uint64),
@@ -88,6 +100,7 @@ EXPORTS = ["tri_pool_workspace_bytes", "tri_pool_create", "tri_pool_destroy", "i
            "ivf_export", "ivf_info", "ivf_destroy", "search_submit", "search_submit_batch", "search_submit_batch_dev",
            "search_step", "search_poll", "search_poll_batch", "search_probes", "search_cancel", "search_sync",
            "search_run_stream", "search_set_policy", "search_get_policy", "tri_policy_split", "tri_policy_slack_order",
+           "tri_policy_feedback", "search_set_feedback", "search_report_signals", "search_get_feedback",
            "tri_pool_kernel_times", "tri_pool_set_profiling", "tri_pool_set_replay", "tri_last_error", "tri_version"]
 
 
@@ -123,6 +136,10 @@ def _load():
     lib.search_get_policy.argtypes = [vp, P(tri_policy), P(ctypes.c_double)]
     lib.tri_policy_split.argtypes = [u32, u32, u32, ctypes.c_float, P(u32), P(u32)]
     lib.tri_policy_slack_order.argtypes = [u32, vp, vp, ctypes.c_int64, ctypes.c_int64, u32, vp]
+    lib.tri_policy_feedback.argtypes = [P(tri_feedback_cfg), P(tri_feedback_signals), P(tri_policy), P(u32)]
+    lib.search_set_feedback.argtypes = [vp, P(tri_feedback_cfg)]
+    lib.search_report_signals.argtypes = [vp, ctypes.c_float, ctypes.c_float]
+    lib.search_get_feedback.argtypes = [vp, P(u64), P(tri_feedback_signals)]
     lib.tri_pool_kernel_times.argtypes = [vp, P(tri_kernel_times), ctypes.c_int]
     lib.tri_pool_set_profiling.argtypes = [vp, u32]
     lib.tri_pool_set_replay.argtypes = [vp, ctypes.c_int]
@@ -340,6 +357,31 @@ def search_get_policy(pool: int):
     pol, t = tri_policy(), ctypes.c_double(0.0)
     _check(_lib.search_get_policy(ctypes.c_void_p(pool), ctypes.byref(pol), ctypes.byref(t)), "search_get_policy")
     return pol, float(t.value)
+
+
+def tri_policy_feedback(cfg: tri_feedback_cfg, signals: tri_feedback_signals, policy: tri_policy):
+    """One period of the control loop: returns (new tri_policy, bit mask of the rules that applied)."""
+    out = tri_policy(policy.high_share, policy.order_high, policy.flush_timeout_s, policy.flush_timeout_high_s)
+    rules = ctypes.c_uint32(0)
+    _check(_lib.tri_policy_feedback(ctypes.byref(cfg), ctypes.byref(signals), ctypes.byref(out), ctypes.byref(rules)),
+           "tri_policy_feedback")
+    return out, int(rules.value)
+
+
+def search_set_feedback(pool: int, cfg: Optional[tri_feedback_cfg]) -> None:
+    _check(_lib.search_set_feedback(ctypes.c_void_p(pool), ctypes.byref(cfg) if cfg is not None else None),
+           "search_set_feedback")
+
+
+def search_report_signals(pool: int, u_kv: float, decode_stall: float) -> None:
+    _check(_lib.search_report_signals(ctypes.c_void_p(pool), u_kv, decode_stall), "search_report_signals")
+
+
+def search_get_feedback(pool: int):
+    """(periods applied, tri_feedback_signals of the last period)."""
+    n, last = ctypes.c_uint64(0), tri_feedback_signals()
+    _check(_lib.search_get_feedback(ctypes.c_void_p(pool), ctypes.byref(n), ctypes.byref(last)), "search_get_feedback")
+    return int(n.value), last
 
 
 def tri_policy_split(free_slots: int, n_high: int, n_low: int, high_share: float):

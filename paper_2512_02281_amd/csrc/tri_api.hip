@@ -168,6 +168,14 @@ struct tri_pool {
     tri_policy policy{1.0f, TRI_ORDER_FIFO, 0.0, 0.0};
     double mean_step_s = 0.0;
     int64_t last_done_ns = 0;
+    // control loop of Sec. 3.3 (search_set_feedback)
+    bool fb_on = false;
+    tri_feedback_cfg fb{};
+    tri_feedback_signals fb_last{};       // what the last period saw
+    float fb_u_kv = __builtin_nanf(""), fb_stall = __builtin_nanf(""), fb_stall_prev = __builtin_nanf("");
+    int64_t fb_last_ns = 0;
+    uint64_t fb_periods = 0;
+    std::vector<float> fb_waits;          // submission-to-admission waits (s) of the high class since the last period
     // search_run_stream: tickets in the order their results arrived
     std::vector<uint32_t> done_log;
     const StreamSink *sink = nullptr;
@@ -176,6 +184,7 @@ struct tri_pool {
 namespace {
 
 void drop_graphs(tri_pool *P);
+void feedback_tick(tri_pool *P);
 
 // Carve the device workspace.  Must match TriDevWs field for field.
 size_t carve(const tri_pool_cfg &c, uint32_t max_row_bytes, uint32_t coarse_rows, uint32_t coarse_ldc,
@@ -905,6 +914,31 @@ void drop_graphs(tri_pool *P)
     }
 }
 
+// One period of the control loop, when it is due: the pool's own measurement (P95 of the high class's
+// waits since the last period) and the reported signals go through tri_policy_feedback.
+void feedback_tick(tri_pool *P)
+{
+    const int64_t t = now_ns();
+    if (P->fb_last_ns && (double)(t - P->fb_last_ns) * 1e-9 < P->fb.period_s) return;
+    if (!P->fb_last_ns) { P->fb_last_ns = t; return; }          // the first period starts now
+    tri_feedback_signals sg{};
+    sg.u_kv = P->fb_u_kv;
+    sg.decode_stall = P->fb_stall;
+    sg.decode_stall_prev = P->fb_stall_prev;
+    sg.wait_p95_s = __builtin_nan("");
+    if (!P->fb_waits.empty()) {
+        const size_t i95 = (size_t)std::min<double>((double)P->fb_waits.size() - 1.0, std::ceil(0.95 * (double)P->fb_waits.size()) - 1.0);
+        std::nth_element(P->fb_waits.begin(), P->fb_waits.begin() + (ptrdiff_t)i95, P->fb_waits.end());
+        sg.wait_p95_s = P->fb_waits[i95];
+    }
+    (void)tri_policy_feedback(&P->fb, &sg, &P->policy, nullptr);
+    P->fb_last = sg;
+    P->fb_stall_prev = P->fb_stall;
+    P->fb_waits.clear();
+    P->fb_last_ns = t;
+    ++P->fb_periods;
+}
+
 // Captured sizes (Sec. 3.2: a step is rounded up to the next captured size, the surplus masked): shape b
 // holds up to slots >> shift and items >> shift, shift = 4, 2, 0.
 struct StepShape { uint32_t slots, items, groups; };
@@ -986,6 +1020,7 @@ extern "C" int search_step(tri_pool *P, tri_step_stats *st)
         if (rc) return rc;
     }
     const tri_pool_cfg &cfg = P->cfg;
+    if (P->fb_on) feedback_tick(P);
 
     // ---- admit (Sec. 3.3): the free slots are split between the classes by the reserved share, the
     //      high class is taken in arrival or least-slack order, the low class first-in first-out
@@ -1030,6 +1065,8 @@ extern "C" int search_step(tri_pool *P, tri_step_stats *st)
                 Ticket &t = P->tickets[ti];
                 t.state = T_RUNNING;
                 t.slot = slot;
+                if (P->fb_on && klass == TRI_CLASS_HIGH && P->fb_waits.size() < (1u << 16))
+                    P->fb_waits.push_back((float)((double)(now_ns() - t.submit_ns) * 1e-9));
                 SlotH &sl = P->slots[slot];
                 sl = SlotH{true, ti, t.nprobe, 0u, t.klass, P->admit_seq++, t.index};
                 P->run_order[t.klass].push_back(slot);
@@ -1375,6 +1412,48 @@ extern "C" int search_get_policy(tri_pool *P, tri_policy *pol, double *mean_step
     std::lock_guard<std::mutex> lk(P->mu);
     if (pol) *pol = P->policy;
     if (mean_step_s) *mean_step_s = P->mean_step_s;
+    return TRI_OK;
+}
+
+extern "C" int search_set_feedback(tri_pool *P, const tri_feedback_cfg *c)
+{
+    if (!P) return fail(TRI_EINVAL, "pool is NULL");
+    std::lock_guard<std::mutex> lk(P->mu);
+    if (!c) { P->fb_on = false; return TRI_OK; }
+    tri_policy probe = P->policy;
+    tri_feedback_signals none{__builtin_nanf(""), __builtin_nanf(""), __builtin_nanf(""), 0.f, __builtin_nan("")};
+    if (!(c->period_s >= 0.0) || !(c->wait_p95_budget_s >= 0.0) || !(c->u_kv_band >= 0.0f) ||
+        tri_policy_feedback(c, &none, &probe, nullptr) != TRI_OK)
+        return fail(TRI_EINVAL, "feedback configuration out of range (0 <= r_min <= r_max <= 1, r_step > 0, tau_factor > 1, "
+                                "0 <= tau_min_s <= tau_max_s, period_s, wait_p95_budget_s, u_kv_band >= 0)");
+    P->fb = *c;
+    P->fb_on = true;
+    P->fb_last_ns = 0;
+    P->fb_periods = 0;
+    P->fb_waits.clear();
+    P->fb_stall_prev = __builtin_nanf("");
+    P->policy.high_share = std::min(std::max(P->policy.high_share, c->r_min), c->r_max);
+    P->policy.flush_timeout_high_s = std::min(std::max(P->policy.flush_timeout_high_s, c->tau_min_s), c->tau_max_s);
+    return TRI_OK;
+}
+
+extern "C" int search_report_signals(tri_pool *P, float u_kv, float decode_stall)
+{
+    if (!P) return fail(TRI_EINVAL, "pool is NULL");
+    if ((u_kv == u_kv && !(u_kv >= 0.0f && u_kv <= 1.0f)) || (decode_stall == decode_stall && !(decode_stall >= 0.0f && decode_stall <= 1.0f)))
+        return fail(TRI_EINVAL, "signals are fractions in [0, 1] (or NaN for unknown)");
+    std::lock_guard<std::mutex> lk(P->mu);
+    P->fb_u_kv = u_kv;
+    P->fb_stall = decode_stall;
+    return TRI_OK;
+}
+
+extern "C" int search_get_feedback(tri_pool *P, uint64_t *periods, tri_feedback_signals *last)
+{
+    if (!P) return fail(TRI_EINVAL, "pool is NULL");
+    std::lock_guard<std::mutex> lk(P->mu);
+    if (periods) *periods = P->fb_periods;
+    if (last) *last = P->fb_last;
     return TRI_OK;
 }
 

@@ -442,6 +442,63 @@ def test_more_probed_lists_than_cached_segments():
         _say(f"many segments: parity {rep}")
 
 
+def test_control_loop_moves_the_policy_inside_the_pool():
+    """Sec. 3.3's control loop run by search_step: reported signals and the pool's own measurement of the
+    high class's waits move the reserved share and the high-class flush time-out in the paper's
+    directions, the admission split follows the moved share, and results stay those of the oracle."""
+    import time
+    tri = harness.lib()
+    cfg = workloads.CONFIGS[0].scaled(n_base=8_000, n_components=32, nlist=32, n_queries=96)
+    base, queries, rows = workloads.make_config01(cfg)
+    fb = tri.tri_feedback_cfg(0.25, 0.75, 0.25, 2.0, 1e-4, 8e-3, 0.9, 0.05, 0.1, 0.0, 50e-6, 0.0)   # period 0: every step
+    with harness.default_pool(tri, slots=8, lists_per_query_step=4, max_dim=cfg.dim, max_outstanding=512) as pool:
+        idx = _build_f32(tri, pool, cfg, base, rows)
+        oidx = harness.oracle_index(tri, idx, base)
+        tri.search_set_policy(pool.handle, high_share=0.0, flush_timeout_high_s=4e-3)
+        tri.search_set_feedback(pool.handle, fb)
+        pol, _ = tri.search_get_policy(pool.handle)
+        assert pol.high_share == 0.25                         # clamped into [r_min, r_max] at once
+        klass = np.r_[np.full(48, tri.TRI_CLASS_HIGH), np.full(48, tri.TRI_CLASS_LOW)].astype(np.uint32)
+        q = tri.make_queries(idx, queries, 10, 16, tri.TRI_L2, klass)
+        tickets, rc = tri.search_submit_batch(pool.handle, q)
+        tri.search_report_signals(pool.handle, 0.5, 0.0)      # KV link starved -> r rises step by step, then tau shrinks
+        shares, taus, waits = [], [], []
+        for _ in range(5):
+            time.sleep(0.001)                                  # (the waiting high-class queries age past the 50 us budget)
+            st = tri.search_step(pool.handle)
+            pol, _ = tri.search_get_policy(pool.handle)
+            shares.append(round(float(pol.high_share), 3))
+            taus.append(pol.flush_timeout_high_s)
+            waits.append(tri.search_get_feedback(pool.handle)[1].wait_p95_s)
+        assert shares == [0.25, 0.5, 0.75, 0.75, 0.75], shares           # (the first call only starts the clock)
+        # tau_pre: halved whenever admitted high-class queries had waited beyond the budget, and once r is at r_max
+        assert taus[0] == 4e-3 and all(b <= a for a, b in zip(taus, taus[1:])) and taus[-1] <= taus[0] / 4, taus
+        assert max(w for w in waits if w == w) > 50e-6, waits
+        periods, last = tri.search_get_feedback(pool.handle)
+        assert periods == 4 and abs(last.u_kv - 0.5) < 1e-6
+        # link at target, decode stalls rising -> r falls again, down to r_min
+        for stall in (0.2, 0.3, 0.4, 0.5):
+            tri.search_report_signals(pool.handle, 0.95, stall)
+            tri.search_step(pool.handle)
+        pol, _ = tri.search_get_policy(pool.handle)
+        assert abs(pol.high_share - 0.25) < 1e-6
+        tri.search_set_feedback(pool.handle, None)
+        tri.search_report_signals(pool.handle, 0.1, 0.0)
+        for _ in range(200):
+            st = tri.search_step(pool.handle)
+            if st.running == 0 and st.pending_high == 0 and st.pending_low == 0 and st.items == 0:
+                break
+        pol2, _ = tri.search_get_policy(pool.handle)
+        assert pol2.high_share == pol.high_share              # switched off: nothing moves any more
+        tri.search_sync(pool.handle)
+        probes = [tri.search_probes(pool.handle, int(t), 16) for t in tickets]
+        ids, dist, n_out, status = tri.search_poll_batch(pool.handle, tickets, 10)
+        assert np.all(status == tri.TRI_OK)
+        harness.compare_with_oracle(oidx, base, queries, 10, 16, 0, ids, dist, n_out, probes)
+        with pytest.raises(Exception):
+            tri.search_report_signals(pool.handle, 1.5, 0.0)
+
+
 def test_scheduling_policy_reservation_slack_and_flush():
     """The step-boundary policy of the paper's Sec. 3.3 on the GPU path: the reserved share splits the free
     slots between the classes, the slack order admits the most urgent high-class query first, flush

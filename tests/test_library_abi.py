@@ -51,6 +51,8 @@ int main(void) {
   printf("%zu %zu %zu %zu %zu\n", sizeof(tri_pool_cfg), sizeof(ivf_params), sizeof(tri_query),
          sizeof(tri_step_stats), sizeof(tri_kernel_times));
   printf("%zu %zu %zu\n", sizeof(tri_policy), sizeof(tri_stream_stats), offsetof(tri_policy, flush_timeout_high_s));
+  printf("%zu %zu %zu %zu ", sizeof(tri_feedback_cfg), sizeof(tri_feedback_signals), offsetof(tri_feedback_cfg, period_s),
+         offsetof(tri_feedback_signals, wait_p95_s));
   printf("%zu %zu %zu %zu\n", offsetof(tri_pool_cfg, score_capacity), offsetof(tri_pool_cfg, hip_stream),
          offsetof(ivf_params, seed), offsetof(tri_query, deadline_ns));
   return 0;
@@ -65,7 +67,9 @@ int main(void) {
                          ctypes.sizeof(tri.tri_step_stats), ctypes.sizeof(tri.tri_kernel_times)]
     assert sizes[5:8] == [ctypes.sizeof(tri.tri_policy), ctypes.sizeof(tri.tri_stream_stats),
                           tri.tri_policy.flush_timeout_high_s.offset]
-    assert sizes[8:] == [tri.tri_pool_cfg.score_capacity.offset, tri.tri_pool_cfg.hip_stream.offset,
+    assert sizes[8:12] == [ctypes.sizeof(tri.tri_feedback_cfg), ctypes.sizeof(tri.tri_feedback_signals),
+                           tri.tri_feedback_cfg.period_s.offset, tri.tri_feedback_signals.wait_p95_s.offset]
+    assert sizes[12:] == [tri.tri_pool_cfg.score_capacity.offset, tri.tri_pool_cfg.hip_stream.offset,
                          tri.ivf_params.seed.offset, tri.tri_query.deadline_ns.offset]
 
 
@@ -159,6 +163,35 @@ def test_slack_order_properties(tri):
         m = int(rng.integers(0, n + 1))                     # only the m most urgent in slack order, the rest by arrival
         assert tri.tri_policy_slack_order(d, e, now, step, m).tolist() == full[:m] + sorted(full[m:])
     assert tri.tri_policy_slack_order(np.zeros(0, np.int64), np.zeros(0, np.uint32), now, step).shape == (0,)
+
+
+def test_feedback_period_matches_the_oracle_rule(tri):
+    """tri_policy_feedback (the library's control-loop period, host only) against oracle/control.py on random
+    signals, unknown ones included, and its argument checks."""
+    import numpy as np
+    from oracle import control
+    ocfg = control.Config(r_min=0.1, r_max=0.8, r_step=0.05, tau_factor=2.0, tau_min_s=1e-4, tau_max_s=8e-3,
+                          u_kv_target=0.9, u_kv_band=0.05, stall_target=0.1, wait_p95_budget_s=2e-3)
+    ccfg = tri.tri_feedback_cfg(ocfg.r_min, ocfg.r_max, ocfg.r_step, ocfg.tau_factor, ocfg.tau_min_s, ocfg.tau_max_s,
+                                ocfg.u_kv_target, ocfg.u_kv_band, ocfg.stall_target, 0.0, ocfg.wait_p95_budget_s, 0.3)
+    rng = np.random.default_rng(5)
+    nan = float("nan")
+    pick = lambda hi: float(rng.choice([nan, float(np.float32(rng.uniform(0, hi))), 0.0, hi]))
+    seen = set()
+    for _ in range(3000):
+        r, tau = float(np.float32(rng.uniform(0, 1))), float(rng.uniform(0, 1e-2))
+        u, st, stp, w = pick(1.0), pick(1.0), pick(1.0), pick(6e-3)
+        want_r, want_tau, want_rules = control.period(ocfg, r, tau, u, st, stp, w)
+        pol, rules = tri.tri_policy_feedback(ccfg, tri.tri_feedback_signals(u, st, stp, 0.0, w),
+                                             tri.tri_policy(r, tri.TRI_ORDER_SLACK, 1e-3, tau))
+        assert float(pol.high_share) == want_r and pol.flush_timeout_high_s == want_tau, (r, tau, u, st, stp, w)
+        assert {i + 1 for i in range(4) if rules >> i & 1} == want_rules
+        assert pol.order_high == tri.TRI_ORDER_SLACK and pol.flush_timeout_s == 1e-3      # untouched
+        seen |= want_rules
+    assert seen == {1, 2, 3, 4}
+    bad = tri.tri_feedback_cfg(0.5, 0.4, 0.05, 2.0, 1e-4, 8e-3, 0.9, 0.05, 0.1, 0.0, 2e-3, 0.3)
+    with pytest.raises(Exception):
+        tri.tri_policy_feedback(bad, tri.tri_feedback_signals(0.5, 0.1, 0.1, 0.0, 1e-3), tri.tri_policy(0.5, 0, 0.0, 1e-3))
 
 
 def test_product_path_never_touches_the_oracle():

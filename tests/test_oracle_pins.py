@@ -291,3 +291,83 @@ def test_planted_mistake_is_caught(name, old, new, monkeypatch):
         except (AssertionError, RuntimeError) as e:   # a mutated oracle may also error out
             fails.append(str(e))
         assert fails, f"planted mistake '{name}' went unnoticed"
+
+
+# ------------------------------------------------------------------------------------------------
+# Control loop of Sec. 3.3 (oracle/control.py).  The paper prints no numbers for it; what it fixes are
+# directions, and those are the pins: none of them re-types the rule.
+def _ctl_cfg(**over):
+    from oracle import control
+    base = dict(r_min=0.1, r_max=0.8, r_step=0.05, tau_factor=2.0, tau_min_s=1e-4, tau_max_s=8e-3,
+                u_kv_target=0.9, u_kv_band=0.05, stall_target=0.1, wait_p95_budget_s=2e-3)
+    base.update(over)
+    return control.Config(**base)
+
+
+def test_control_loop_follows_the_papers_directions():
+    from oracle import control
+    cfg = _ctl_cfg()
+    rng = np.random.default_rng(11)
+    nan = float("nan")
+    for _ in range(2000):
+        r = float(rng.uniform(0.0, 1.0))
+        tau = float(rng.uniform(0.0, 1e-2))
+        u = float(rng.uniform(0, 1)) if rng.random() < 0.8 else nan
+        st = float(rng.uniform(0, 1)) if rng.random() < 0.8 else nan
+        stp = float(rng.uniform(0, 1)) if rng.random() < 0.8 else nan
+        w = float(rng.uniform(0, 6e-3)) if rng.random() < 0.8 else nan
+        r0 = min(max(r, cfg.r_min), cfg.r_max)
+        t0 = min(max(tau, cfg.tau_min_s), cfg.tau_max_s)
+        r1, t1, _ = control.period(cfg, r, tau, u, st, stp, w)
+        # bounds, always
+        assert cfg.r_min - 1e-6 <= r1 <= cfg.r_max + 1e-6 and cfg.tau_min_s <= t1 <= cfg.tau_max_s
+        # one period moves r by at most one step and tau by at most two factors
+        assert abs(r1 - r0) <= cfg.r_step + 1e-6 and t0 / cfg.tau_factor ** 2 - 1e-12 <= t1 <= t0 * cfg.tau_factor + 1e-12
+        if u == u and u < cfg.u_kv_target - cfg.u_kv_band - 1e-6:
+            # link under-used: prefill is accelerated -- r never falls, tau_pre never grows, and one of them moves
+            # unless both are at their limits; decode stalls cannot take share away in the same period
+            assert r1 >= r0 - 1e-7 and t1 <= t0 + 1e-15
+            assert r1 > r0 or t1 < t0 or (r0 >= cfg.r_max - 1e-6 and t0 <= cfg.tau_min_s)
+        elif st == st and stp == stp and st > cfg.stall_target + 1e-6 and st > stp + 1e-6 and u == u \
+                and u > cfg.u_kv_target - cfg.u_kv_band + 1e-6:
+            # link fine, decode stalls rising: r falls (until r_min)
+            assert r1 < r0 or r0 <= cfg.r_min + 1e-6
+        if w == w and w > cfg.wait_p95_budget_s:
+            assert t1 < t0 or t0 <= cfg.tau_min_s                  # waits over budget: tau_pre is shortened
+
+
+def test_control_loop_fixed_point_and_relaxation():
+    from oracle import control
+    cfg = _ctl_cfg()
+    # everything on target, waits well inside the budget: r stays, tau_pre relaxes to its upper bound and stays
+    r, tau = 0.4, 1e-3
+    for _ in range(10):
+        r, tau, rules = control.period(cfg, r, tau, 0.95, 0.05, 0.05, 0.5e-3)
+        assert rules == {4}
+    assert abs(r - 0.4) < 1e-6 and tau == cfg.tau_max_s
+    # waits between half the budget and the budget: nothing moves at all
+    r2, tau2, rules = control.period(cfg, 0.4, 1e-3, 0.95, 0.05, 0.05, 1.5e-3)
+    assert (abs(r2 - 0.4) < 1e-6, tau2, rules) == (True, 1e-3, set())
+    # a stall level above target that is NOT rising does not move r (the paper speaks of rising stalls)
+    r3, _, rules = control.period(cfg, 0.4, 1e-3, 0.95, 0.3, 0.3, 1.5e-3)
+    assert abs(r3 - 0.4) < 1e-6 and 3 not in rules
+
+
+def test_control_loop_settles_against_a_toy_plant():
+    """Closed loop: a plant in which the KV link fills with the prefill share (u_kv = r / 0.5, capped) and
+    decode stalls grow once prefill takes more than 0.6 of a batch.  From either end r moves into the
+    window where the link is at target and stalls are not rising, and stays there."""
+    from oracle import control
+    cfg = _ctl_cfg()
+    for r_start in (cfg.r_min, cfg.r_max):
+        r, tau, stall_prev = r_start, 4e-3, 0.0
+        trace = []
+        for _ in range(60):
+            u = min(1.0, r / 0.5)
+            stall = max(0.0, (r - 0.6)) * 2.0 + 0.05 + (0.01 if r > 0.6 else 0.0) * len(trace)   # keeps rising while r > 0.6
+            r, tau, _ = control.period(cfg, r, tau, u, stall, stall_prev, 1e-3)
+            stall_prev = stall
+            trace.append(r)
+        tail = trace[-20:]
+        assert max(tail) - min(tail) < 1e-6, f"r still moving: {tail}"
+        assert 0.5 * (cfg.u_kv_target - cfg.u_kv_band) - 1e-6 <= tail[-1] <= 0.6 + 1e-6, tail[-1]
