@@ -1,0 +1,780 @@
+// The paper's own engine (Sec. 3.2): continuous batching of best-first searches over a fixed-degree
+// neighbour graph, one "extend" of every running request per step.  Per request and on the device: a
+// candidate list topM (sorted composites of score key, id and an "expanded" mark), a visited bit table
+// (one bit per database row, so "first seen" is exact), its query row.  A step is four fixed-shape
+// launches over all S slots -- idle slots leave at once, which is the masked padding of the paper's
+// fixed-shape task array:
+//   extend   : up to p non-expanded parents of topM, their D neighbours, visited filter -> compacted
+//              distance tasks of the slot (at most p * D);
+//   distance : every task = one gathered row against the slot's query, 16 lanes per task;
+//   merge    : tasks' (score, id) + topM -> new topM by rank counting; stop rule; finished requests write
+//              their record into the step's pinned result block.
+// Newly admitted requests take the place of `extend` with their entry points as tasks.
+#include "../../include/trinity_graph.h"
+#include "tri_common.h"
+
+#include <algorithm>
+#include <chrono>
+#include <cstring>
+#include <deque>
+#include <mutex>
+#include <new>
+#include <vector>
+
+namespace {
+
+constexpr uint32_t GRING = 4;
+constexpr uint32_t GX_THREADS = 256;
+constexpr uint32_t GX_TEAM = 16;                 // lanes that share one distance task
+
+struct GxMeta {          // per slot
+    uint32_t k, metric;
+    uint32_t state;      // 0 idle, 1 running
+    uint32_t fresh;      // admitted in this step: its tasks are the entry points, no extend yet
+    uint32_t iters, evals;
+    uint32_t n_par;      // parents selected by this step's extend
+    uint32_t n_tasks;    // distance tasks of this step
+};
+
+struct GxNewDesc {       // one admitted query in the step's upload block
+    uint32_t slot, k, metric, pad_;
+    uint64_t src_dev;    // GPU address of the query's vector
+    uint64_t pad2_;
+};
+
+struct GxHdr {           // head of the upload block
+    uint32_t n16;        // 16-byte pieces to pull (this header + the admission records)
+    uint32_t n_new;
+    uint32_t pad_[2];
+};
+
+// A step's result block (pinned host memory, written with plain stores only): done[S] -- set to 1 by a
+// slot that finished in the step, cleared by the host before the step is enqueued -- then S records
+// [n, iters, evals, 0, ids[M], score bits[M]], record s for slot s.
+
+struct GxDev {           // everything the kernels need, by value
+    const uint8_t *vecs;
+    const float *vnorm;
+    const uint32_t *graph;
+    const uint32_t *seeds;
+    uint8_t *slot_q;
+    float *qnorm;
+    GxMeta *meta;
+    unsigned long long *topm;
+    uint32_t *visited;
+    uint32_t *tasks;
+    float *tdist;
+    uint8_t *upload;
+    uint64_t n;
+    uint32_t dim, dtype, row_pitch, degree, n_seeds;
+    uint32_t S, M, p, T, vwords, max_iters;
+};
+
+__device__ __forceinline__ uint32_t gx_key(float f, uint32_t descending)
+{
+    uint32_t u = __float_as_uint(f);
+    if (u == 0x80000000u) u = 0;
+    u ^= (u >> 31) ? 0xFFFFFFFFu : 0x80000000u;
+    return descending ? ~u : u;
+}
+
+__device__ __forceinline__ float gx_unkey(uint32_t key, uint32_t descending)
+{
+    uint32_t u = descending ? ~key : key;
+    u ^= (u >> 31) ? 0x80000000u : 0xFFFFFFFFu;
+    return __uint_as_float(u);
+}
+
+// Position of this thread's element among the elements of the workgroup (256 threads) whose flag is set,
+// in thread order; *total = how many are set.  wave_cnt: 4 words of shared memory.  Two barriers.
+__device__ __forceinline__ uint32_t gx_block_rank(bool flag, uint32_t *wave_cnt, uint32_t *total)
+{
+    const uint32_t lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const unsigned long long m = __ballot(flag);
+    __syncthreads();                          // (wave_cnt may still be read from a previous use)
+    if (lane == 0) wave_cnt[wave] = (uint32_t)__popcll(m);
+    __syncthreads();
+    uint32_t base = 0;
+    for (uint32_t w = 0; w < wave; ++w) base += wave_cnt[w];
+    *total = wave_cnt[0] + wave_cnt[1] + wave_cnt[2] + wave_cnt[3];
+    return base + (uint32_t)__popcll(m & ((1ull << lane) - 1ull));
+}
+
+__global__ void gx_pull_kernel(uint4 *__restrict__ dst, const uint4 *__restrict__ src_host)
+{
+    const size_t n16 = ((const GxHdr *)src_host)->n16;
+    const size_t stride = (size_t)gridDim.x * blockDim.x;
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n16; i += stride) dst[i] = src_host[i];
+}
+
+// ------------------------------------------------------------------------------------------ admit
+// One workgroup per admitted query: its zero-padded row and |q|^2 into the slot, visited cleared, topM
+// emptied, the entry points (first-seen only) as the slot's tasks of this step.
+template <typename T>
+__device__ __forceinline__ float gx_admit_row(const T *src, T *dst, uint32_t dim, uint32_t dpad)
+{
+    float part = 0.f;
+    for (uint32_t e = threadIdx.x; e < dpad; e += GX_THREADS) {
+        const T v = e < dim ? src[e] : (T)0;
+        dst[e] = v;
+        const float f = (float)v;
+        part += f * f;
+    }
+    return part;
+}
+
+__global__ __launch_bounds__(GX_THREADS) void gx_admit_kernel(GxDev D)
+{
+    __shared__ float red[GX_THREADS];
+    __shared__ uint32_t wave_cnt[4];
+    const GxHdr *hdr = (const GxHdr *)D.upload;
+    if (blockIdx.x >= hdr->n_new) return;
+    const GxNewDesc d = ((const GxNewDesc *)(D.upload + sizeof(GxHdr)))[blockIdx.x];
+    const uint32_t s = d.slot, tid = threadIdx.x;
+    uint8_t *qrow = D.slot_q + (size_t)s * D.row_pitch;
+    red[tid] = D.dtype == TRI_F16
+                   ? gx_admit_row<_Float16>((const _Float16 *)d.src_dev, (_Float16 *)qrow, D.dim, D.row_pitch / 2)
+                   : gx_admit_row<float>((const float *)d.src_dev, (float *)qrow, D.dim, D.row_pitch / 4);
+    uint4 *vis = (uint4 *)(D.visited + (size_t)s * D.vwords);
+    for (uint32_t i = tid; i < D.vwords / 4; i += GX_THREADS) vis[i] = make_uint4(0u, 0u, 0u, 0u);
+    for (uint32_t i = tid; i < D.M; i += GX_THREADS) D.topm[(size_t)s * D.M + i] = ~0ull;
+    __syncthreads();
+    for (uint32_t w = GX_THREADS / 2; w > 0; w >>= 1) {
+        if (tid < w) red[tid] += red[tid + w];
+        __syncthreads();
+    }
+    // entry points: thread j takes seed j (n_seeds <= 256)
+    uint32_t v = TRI_GRAPH_PAD;
+    if (tid < D.n_seeds) {
+        const uint32_t c = D.seeds[tid];
+        if (c < D.n) {
+            const uint32_t bit = 1u << (c & 31);
+            const uint32_t old = atomicOr(&D.visited[(size_t)s * D.vwords + (c >> 5)], bit);
+            if (!(old & bit)) v = c;
+        }
+    }
+    uint32_t total;
+    const uint32_t pos = gx_block_rank(v != TRI_GRAPH_PAD, wave_cnt, &total);
+    if (v != TRI_GRAPH_PAD) D.tasks[(size_t)s * D.T + pos] = v;
+    if (tid == 0) {
+        D.qnorm[s] = red[0];
+        D.meta[s] = GxMeta{d.k, d.metric, 1u, 1u, 0u, total, 0u, total};
+    }
+}
+
+// ------------------------------------------------------------------------------------------ extend
+// One workgroup per slot.  Thread i looks at topM entry i: the first p non-expanded ones (in topM's order)
+// become parents and are marked; thread t then takes neighbour t % D of parent t / D through the visited
+// filter; the survivors are compacted into the slot's task list.
+__global__ __launch_bounds__(GX_THREADS) void gx_extend_kernel(GxDev D)
+{
+    __shared__ uint32_t wave_cnt[4];
+    __shared__ uint32_t parent[TRI_GRAPH_TASK_LIMIT];
+    const uint32_t s = blockIdx.x, tid = threadIdx.x;
+    GxMeta *m = D.meta + s;
+    if (m->state != 1u || m->fresh) return;               // (idle: masked; fresh: its tasks are the entry points)
+    unsigned long long e = ~0ull;
+    if (tid < D.M) e = D.topm[(size_t)s * D.M + tid];
+    const bool unexp = e != ~0ull && !(e & 1ull);
+    uint32_t total;
+    const uint32_t rank = gx_block_rank(unexp, wave_cnt, &total);
+    if (unexp && rank < D.p) {
+        parent[rank] = (uint32_t)(e & 0xFFFFFFFFull) >> 1;
+        D.topm[(size_t)s * D.M + tid] = e | 1ull;
+    }
+    const uint32_t n_par = total < D.p ? total : D.p;
+    __syncthreads();
+    uint32_t v = TRI_GRAPH_PAD;
+    const uint32_t par = tid / D.degree, j = tid % D.degree;
+    if (par < n_par) {
+        const uint32_t c = D.graph[(size_t)parent[par] * D.degree + j];
+        if (c < D.n) {
+            const uint32_t bit = 1u << (c & 31);
+            const uint32_t old = atomicOr(&D.visited[(size_t)s * D.vwords + (c >> 5)], bit);
+            if (!(old & bit)) v = c;
+        }
+    }
+    uint32_t n_tasks;
+    const uint32_t pos = gx_block_rank(v != TRI_GRAPH_PAD, wave_cnt, &n_tasks);
+    if (v != TRI_GRAPH_PAD) D.tasks[(size_t)s * D.T + pos] = v;
+    if (tid == 0) {
+        m->n_par = n_par;
+        m->n_tasks = n_tasks;
+        m->evals += n_tasks;
+    }
+}
+
+// ------------------------------------------------------------------------------------------ distance
+// One workgroup per slot, the slot's query row in LDS; a team of 16 lanes per task reads the task's row
+// in 256-byte pieces (16 bytes per lane, consecutive lanes consecutive addresses: two full 128-byte
+// lines per piece) and reduces its dot product in a fixed order, so a score does not depend on which
+// other tasks share the launch.  L2 = |x|^2 + |q|^2 - 2 x.q with the stored |x|^2.
+// NCH = 256-byte pieces per row when known at compile time (all loads of a row in flight together), 0 = any.
+template <int DT>
+__device__ __forceinline__ float gx_dot16(const uint4 &x, const uint4 &q, float acc)
+{
+    if (DT == TRI_F16) {
+        typedef _Float16 h2 __attribute__((ext_vector_type(2)));
+        const h2 *a = (const h2 *)&x, *b = (const h2 *)&q;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) acc = __builtin_amdgcn_fdot2(a[i], b[i], acc, false);
+    } else {
+        const float *a = (const float *)&x, *b = (const float *)&q;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) acc = fmaf(a[i], b[i], acc);
+    }
+    return acc;
+}
+
+template <int DT, int NCH>
+__global__ __launch_bounds__(GX_THREADS) void gx_distance_kernel(GxDev D)
+{
+    extern __shared__ __attribute__((aligned(16))) uint8_t gx_q[];
+    const uint32_t s = blockIdx.x, tid = threadIdx.x;
+    const GxMeta m = D.meta[s];
+    if (m.state != 1u || m.n_tasks == 0) return;
+    const uint32_t pieces = D.row_pitch / 16;
+    for (uint32_t i = tid; i < pieces; i += GX_THREADS)
+        ((uint4 *)gx_q)[i] = ((const uint4 *)(D.slot_q + (size_t)s * D.row_pitch))[i];
+    __syncthreads();
+    const uint32_t team = tid / GX_TEAM, c = tid % GX_TEAM;
+    const float qn = D.qnorm[s];
+    const uint32_t nch = NCH ? (uint32_t)NCH : D.row_pitch / 256;
+    for (uint32_t t = team; t < m.n_tasks; t += GX_THREADS / GX_TEAM) {
+        const uint32_t id = D.tasks[(size_t)s * D.T + t];
+        const uint4 *row = (const uint4 *)(D.vecs + (size_t)id * D.row_pitch);
+        float acc = 0.f;
+        if (NCH) {
+            uint4 x[NCH ? NCH : 1];
+#pragma unroll
+            for (int i = 0; i < NCH; ++i) x[i] = row[c + i * GX_TEAM];
+#pragma unroll
+            for (int i = 0; i < NCH; ++i) acc = gx_dot16<DT>(x[i], ((const uint4 *)gx_q)[c + i * GX_TEAM], acc);
+        } else {
+            for (uint32_t i = 0; i < nch; ++i) acc = gx_dot16<DT>(row[c + i * GX_TEAM], ((const uint4 *)gx_q)[c + i * GX_TEAM], acc);
+        }
+#pragma unroll
+        for (int d = GX_TEAM / 2; d > 0; d >>= 1) acc += __shfl_xor(acc, d, GX_TEAM);
+        if (c == 0) D.tdist[(size_t)s * D.T + t] = m.metric == TRI_L2 ? (D.vnorm[id] + qn) - 2.0f * acc : acc;
+    }
+}
+
+// ------------------------------------------------------------------------------------------ merge
+// One workgroup per slot: the step's (score, id) pairs and topM, as composites (key << 32 | id << 1 |
+// expanded; ids are unique: a row is scored at most once per request), are ranked by counting; the first
+// M form the new topM.  topM changed iff one of the new pairs ranks among the first M.
+__global__ __launch_bounds__(GX_THREADS) void gx_merge_kernel(GxDev D, uint32_t *__restrict__ done, uint32_t *__restrict__ rec_base,
+                                                              uint32_t rec_words)
+{
+    __shared__ unsigned long long el[TRI_GRAPH_TOPM_LIMIT + TRI_GRAPH_TASK_LIMIT];
+    __shared__ unsigned long long out[TRI_GRAPH_TOPM_LIMIT];
+    __shared__ uint32_t changed;
+    __shared__ uint32_t n_sh;
+    const uint32_t s = blockIdx.x, tid = threadIdx.x;
+    GxMeta *mp = D.meta + s;
+    const GxMeta m = *mp;
+    if (m.state != 1u) return;
+    const uint32_t desc = m.metric == TRI_IP;
+    const uint32_t nt = m.n_tasks, n_el = D.M + nt;
+    if (tid == 0) { changed = 0; n_sh = 0; }
+    for (uint32_t i = tid; i < n_el; i += GX_THREADS) {
+        unsigned long long e;
+        if (i < D.M) e = D.topm[(size_t)s * D.M + i];
+        else {
+            const uint32_t t = i - D.M;
+            e = ((unsigned long long)gx_key(D.tdist[(size_t)s * D.T + t], desc) << 32) |
+                ((unsigned long long)D.tasks[(size_t)s * D.T + t] << 1);
+        }
+        el[i] = e;
+    }
+    for (uint32_t i = tid; i < D.M; i += GX_THREADS) out[i] = ~0ull;
+    __syncthreads();
+    for (uint32_t i = tid; i < n_el; i += GX_THREADS) {
+        const unsigned long long e = el[i];
+        if (e == ~0ull) continue;                       // empty topM entries stay at the end
+        uint32_t r = 0;
+        for (uint32_t j = 0; j < n_el; ++j) r += el[j] < e;
+        if (r < D.M) {
+            out[r] = e;
+            if (i >= D.M) changed = 1u;                 // (benign race: every writer stores 1)
+        }
+    }
+    __syncthreads();
+    for (uint32_t i = tid; i < D.M; i += GX_THREADS) D.topm[(size_t)s * D.M + i] = out[i];
+    // stop rule
+    bool finish;
+    uint32_t iters = m.iters;
+    if (m.fresh) finish = D.max_iters == 0;
+    else if (m.n_par == 0) finish = true;               // no parent left: not an extend
+    else {
+        iters += 1;
+        finish = !changed || iters >= D.max_iters;
+    }
+    if (finish) {
+        uint32_t *rec = rec_base + (size_t)s * rec_words;
+        uint32_t n_valid = 0;
+        for (uint32_t i = tid; i < D.M; i += GX_THREADS) {
+            const unsigned long long e = out[i];
+            const bool ok = e != ~0ull && i < m.k;
+            rec[4 + i] = ok ? (uint32_t)(e & 0xFFFFFFFFull) >> 1 : 0xFFFFFFFFu;
+            rec[4 + D.M + i] = ok ? __float_as_uint(gx_unkey((uint32_t)(e >> 32), desc)) : 0u;
+            n_valid += ok;
+        }
+        if (n_valid) atomicAdd(&n_sh, n_valid);          // n = valid entries among the first k
+        __syncthreads();
+        if (tid == 0) {
+            rec[0] = n_sh; rec[1] = iters; rec[2] = m.evals; rec[3] = 0u;
+            mp->state = 0u;
+            __threadfence_system();                       // the record before the mark the host looks for
+            done[s] = 1u;
+        }
+    } else if (tid == 0) {
+        mp->iters = iters;
+        mp->fresh = 0u;
+    }
+}
+
+// ================================================================================== host side
+inline int64_t gnow_ns()
+{
+    return std::chrono::duration_cast<std::chrono::nanoseconds>(std::chrono::steady_clock::now().time_since_epoch()).count();
+}
+inline size_t gup(size_t v, size_t m) { return (v + m - 1) / m * m; }
+
+enum GState : uint8_t { G_FREE = 0, G_PENDING, G_RUNNING, G_DONE };
+
+struct GTicket {
+    uint32_t gen = 0;
+    GState state = G_FREE;
+    uint32_t k = 0, metric = 0, klass = 0, slot = 0;
+    const void *dev_vec = nullptr;
+    uint32_t n_out = 0, iters = 0, evals = 0;
+};
+
+struct GStep {
+    bool in_use = false;
+    bool profiled = false;
+    uint64_t seq = 0;
+    hipEvent_t done = nullptr, ev0 = nullptr, ev1 = nullptr;
+    uint8_t *up_host = nullptr, *up_dev = nullptr;
+    uint8_t *down_host = nullptr, *down_dev = nullptr;
+};
+
+#define GHIP(expr)                                                                                   \
+    do {                                                                                             \
+        hipError_t e_ = (expr);                                                                      \
+        if (e_ != hipSuccess) return tri_fail(TRI_EHIP, "%s -> %s", #expr, hipGetErrorString(e_));   \
+    } while (0)
+
+}  // namespace
+
+struct tri_gpool {
+    tri_graph_cfg cfg{};
+    int device = 0;
+    hipStream_t stream = nullptr;
+    std::mutex mu;
+    GxDev D{};
+    uint32_t depth = 2, rec_words = 0;
+    size_t up_bytes = 0, down_bytes = 0;
+    uint8_t *pinned = nullptr, *qstore = nullptr, *qstore_dev = nullptr;
+    std::vector<GTicket> tickets;
+    std::vector<uint32_t> free_tickets, free_slots, slot_ticket;
+    std::vector<uint32_t> res_ids;
+    std::vector<float> res_score;
+    std::deque<uint32_t> pending[2];
+    uint32_t n_running = 0;
+    uint64_t step_seq = 0;
+    GStep ring[GRING];
+    tri_graph_times times{};
+};
+
+namespace {
+
+struct GLayout {
+    size_t vecs, vnorm, graph, seeds, slot_q, qnorm, meta, topm, visited, tasks, tdist, upload, total;
+    uint32_t row_pitch, vwords, T;
+};
+
+int g_validate(const tri_graph_cfg *c, uint64_t n, uint32_t dim, uint32_t degree, uint32_t dtype)
+{
+    if (!c) return tri_fail(TRI_EINVAL, "cfg is NULL");
+    if (c->slots == 0 || c->slots > (1u << 16)) return tri_fail(TRI_EINVAL, "slots must be 1..65536");
+    if (c->topm == 0 || c->topm > TRI_GRAPH_TOPM_LIMIT) return tri_fail(TRI_EINVAL, "topm must be 1..%u", TRI_GRAPH_TOPM_LIMIT);
+    if (degree == 0 || c->parents == 0 || (uint64_t)c->parents * degree > TRI_GRAPH_TASK_LIMIT)
+        return tri_fail(TRI_EINVAL, "need parents >= 1, degree >= 1 and parents * degree <= %u", TRI_GRAPH_TASK_LIMIT);
+    if (c->max_outstanding < c->slots) return tri_fail(TRI_EINVAL, "max_outstanding must be >= slots");
+    if (c->depth > GRING) return tri_fail(TRI_EINVAL, "depth must be 0..%u", GRING);
+    if (n == 0 || n >= (1ull << 31)) return tri_fail(TRI_EINVAL, "n must be 1..2^31-1");
+    if (dtype != TRI_F32 && dtype != TRI_F16) return tri_fail(TRI_EINVAL, "dtype must be TRI_F32 or TRI_F16");
+    if (dim == 0 || gup((size_t)dim * (dtype == TRI_F16 ? 2 : 4), 256) > TRI_MAX_ROW_BYTES)
+        return tri_fail(TRI_EINVAL, "dim out of range: a padded row may have at most %u bytes", TRI_MAX_ROW_BYTES);
+    return TRI_OK;
+}
+
+GLayout g_layout(const tri_graph_cfg &c, uint64_t n, uint32_t dim, uint32_t degree, uint32_t dtype)
+{
+    GLayout L{};
+    L.row_pitch = (uint32_t)gup((size_t)dim * (dtype == TRI_F16 ? 2 : 4), 256);
+    L.vwords = (uint32_t)gup((n + 31) / 32, 4);
+    L.T = TRI_GRAPH_TASK_LIMIT;
+    size_t o = 0;
+    auto take = [&](size_t bytes) { size_t at = o; o = gup(o + bytes, 256); return at; };
+    const size_t S = c.slots;
+    L.vecs = take(n * L.row_pitch);
+    L.vnorm = take(n * 4);
+    L.graph = take(n * degree * 4);
+    L.seeds = take(TRI_GRAPH_TASK_LIMIT * 4);
+    L.slot_q = take(S * L.row_pitch);
+    L.qnorm = take(S * 4);
+    L.meta = take(S * sizeof(GxMeta));
+    L.topm = take(S * c.topm * 8);
+    L.visited = take(S * L.vwords * 4);
+    L.tasks = take(S * L.T * 4);
+    L.tdist = take(S * L.T * 4);
+    L.upload = take(sizeof(GxHdr) + S * sizeof(GxNewDesc));
+    L.total = o;
+    return L;
+}
+
+// Collect the records of completed steps, oldest first.  block: wait for all of them.
+int g_reap(tri_gpool *P, bool block, uint32_t *finished)
+{
+    for (uint32_t it = 0; it < GRING; ++it) {
+        GStep *R = nullptr;
+        for (uint32_t i = 0; i < GRING; ++i)
+            if (P->ring[i].in_use && (!R || P->ring[i].seq < R->seq)) R = &P->ring[i];
+        if (!R) break;
+        if (block) {
+            GHIP(hipEventSynchronize(R->done));
+        } else {
+            const hipError_t q = hipEventQuery(R->done);
+            if (q == hipErrorNotReady) break;
+            if (q != hipSuccess) return tri_fail(TRI_EHIP, "hipEventQuery -> %s", hipGetErrorString(q));
+        }
+        const uint32_t *done = (const uint32_t *)R->down_host;
+        const uint32_t *recs = done + P->cfg.slots;
+        const uint32_t M = P->cfg.topm;
+        uint64_t tasks = 0;
+        for (uint32_t slot = 0; slot < P->cfg.slots; ++slot) {
+            if (!done[slot]) continue;
+            const uint32_t *rec = recs + (size_t)slot * P->rec_words;
+            const uint32_t ti = P->slot_ticket[slot];
+            GTicket &t = P->tickets[ti];
+            t.n_out = rec[0]; t.iters = rec[1]; t.evals = rec[2];
+            tasks += t.evals;
+            memcpy(&P->res_ids[(size_t)ti * M], rec + 4, (size_t)t.n_out * 4);
+            memcpy(&P->res_score[(size_t)ti * M], rec + 4 + M, (size_t)t.n_out * 4);
+            t.state = G_DONE;
+            P->free_slots.push_back(slot);
+            --P->n_running;
+            if (finished) ++*finished;
+        }
+        if (R->profiled) {
+            float ms = 0.f;
+            GHIP(hipEventElapsedTime(&ms, R->ev0, R->ev1));
+            P->times.steps += 1;
+            P->times.distance_ms += ms;
+            P->times.tasks += tasks;        // (tasks of the requests that finished in the step: over a run from idle
+                                            //  to idle this adds up to every task scored)
+        }
+        R->in_use = false;
+    }
+    return TRI_OK;
+}
+
+template <int DT>
+hipError_t g_launch_distance(const tri_gpool *P)
+{
+    const GxDev &D = P->D;
+    const dim3 grid(D.S), block(GX_THREADS);
+    const size_t lds = D.row_pitch;
+    switch (D.row_pitch / 256) {
+    case 2: hipLaunchKernelGGL((gx_distance_kernel<DT, 2>), grid, block, lds, P->stream, D); break;
+    case 6: hipLaunchKernelGGL((gx_distance_kernel<DT, 6>), grid, block, lds, P->stream, D); break;
+    default: hipLaunchKernelGGL((gx_distance_kernel<DT, 0>), grid, block, lds, P->stream, D); break;
+    }
+    return hipGetLastError();
+}
+
+}  // namespace
+
+extern "C" int graph_pool_bytes(const tri_graph_cfg *cfg, uint64_t n, uint32_t dim, uint32_t degree, uint32_t dtype,
+                                size_t *dev_bytes)
+{
+    const int rc = g_validate(cfg, n, dim, degree, dtype);
+    if (rc) return rc;
+    if (!dev_bytes) return tri_fail(TRI_EINVAL, "dev_bytes is NULL");
+    *dev_bytes = g_layout(*cfg, n, dim, degree, dtype).total;
+    return TRI_OK;
+}
+
+// |x|^2 of every stored row (fixed order per row: lane-strided partial sums, then a tree).
+__global__ void gx_row_norm_kernel(const uint8_t *__restrict__ vecs, uint32_t row_pitch, uint32_t dtype, uint64_t n,
+                                   float *__restrict__ out)
+{
+    const uint64_t row = (uint64_t)blockIdx.x * (blockDim.x / 64) + threadIdx.x / 64;
+    if (row >= n) return;
+    const uint32_t lane = threadIdx.x & 63;
+    float acc = 0.f;
+    if (dtype == TRI_F16) {
+        const _Float16 *r = (const _Float16 *)(vecs + row * row_pitch);
+        for (uint32_t e = lane; e < row_pitch / 2; e += 64) { const float f = (float)r[e]; acc += f * f; }
+    } else {
+        const float *r = (const float *)(vecs + row * row_pitch);
+        for (uint32_t e = lane; e < row_pitch / 4; e += 64) acc += r[e] * r[e];
+    }
+    for (int d = 32; d > 0; d >>= 1) acc += __shfl_xor(acc, d, 64);
+    if (lane == 0) out[row] = acc;
+}
+
+extern "C" int graph_pool_create(const tri_graph_cfg *cfg, const void *vectors, const uint32_t *neighbors, uint64_t n,
+                                 uint32_t dim, uint32_t degree, uint32_t dtype, const uint32_t *seeds, uint32_t n_seeds,
+                                 void *dev_mem, size_t dev_bytes, tri_gpool **out)
+{
+    int rc = g_validate(cfg, n, dim, degree, dtype);
+    if (rc) return rc;
+    if (!vectors || !neighbors || !dev_mem || !out || (!seeds && n_seeds)) return tri_fail(TRI_EINVAL, "NULL argument");
+    if (n_seeds == 0 || n_seeds > TRI_GRAPH_TASK_LIMIT) return tri_fail(TRI_EINVAL, "n_seeds must be 1..%u", TRI_GRAPH_TASK_LIMIT);
+    if ((uintptr_t)dev_mem % 256) return tri_fail(TRI_EINVAL, "dev_mem must be 256-byte aligned");
+    const GLayout L = g_layout(*cfg, n, dim, degree, dtype);
+    if (dev_bytes < L.total) return tri_fail(TRI_ENOMEM, "dev_mem has %zu bytes, %zu needed", dev_bytes, L.total);
+    tri_gpool *P = new (std::nothrow) tri_gpool();
+    if (!P) return tri_fail(TRI_ENOMEM, "out of host memory");
+    P->cfg = *cfg;
+    P->depth = cfg->depth ? cfg->depth : 2u;
+    P->stream = (hipStream_t)cfg->hip_stream;
+    hipError_t e = hipGetDevice(&P->device);
+    if (e != hipSuccess) { delete P; return tri_fail(TRI_EHIP, "hipGetDevice -> %s", hipGetErrorString(e)); }
+    uint8_t *base = (uint8_t *)dev_mem;
+    GxDev &D = P->D;
+    D.vecs = base + L.vecs; D.vnorm = (float *)(base + L.vnorm); D.graph = (uint32_t *)(base + L.graph);
+    D.seeds = (uint32_t *)(base + L.seeds); D.slot_q = base + L.slot_q; D.qnorm = (float *)(base + L.qnorm);
+    D.meta = (GxMeta *)(base + L.meta); D.topm = (unsigned long long *)(base + L.topm);
+    D.visited = (uint32_t *)(base + L.visited); D.tasks = (uint32_t *)(base + L.tasks); D.tdist = (float *)(base + L.tdist);
+    D.upload = base + L.upload;
+    D.n = n; D.dim = dim; D.dtype = dtype; D.row_pitch = L.row_pitch; D.degree = degree; D.n_seeds = n_seeds;
+    D.S = cfg->slots; D.M = cfg->topm; D.p = cfg->parents; D.T = L.T; D.vwords = L.vwords; D.max_iters = cfg->max_iters;
+    // index data: rows padded with zeros, neighbour list, entry points, row norms, idle slots
+    const size_t es = dtype == TRI_F16 ? 2 : 4;
+    hipStream_t s = P->stream;
+    e = hipMemsetAsync(base + L.vecs, 0, n * L.row_pitch, s);
+    if (e == hipSuccess) e = hipMemcpy2DAsync(base + L.vecs, L.row_pitch, vectors, (size_t)dim * es, (size_t)dim * es, n, hipMemcpyDefault, s);
+    if (e == hipSuccess) e = hipMemcpyAsync(base + L.graph, neighbors, n * degree * 4, hipMemcpyDefault, s);
+    if (e == hipSuccess) e = hipMemcpyAsync(base + L.seeds, seeds, (size_t)n_seeds * 4, hipMemcpyHostToDevice, s);
+    if (e == hipSuccess) e = hipMemsetAsync(base + L.meta, 0, (size_t)cfg->slots * sizeof(GxMeta), s);
+    if (e == hipSuccess) {
+        hipLaunchKernelGGL(gx_row_norm_kernel, dim3((unsigned)((n + 3) / 4)), dim3(256), 0, s, D.vecs, D.row_pitch, dtype, n,
+                           (float *)(base + L.vnorm));
+        e = hipGetLastError();
+    }
+    if (e == hipSuccess) e = hipStreamSynchronize(s);
+    if (e != hipSuccess) { delete P; return tri_fail(TRI_EHIP, "index upload -> %s", hipGetErrorString(e)); }
+    // pinned blocks
+    P->rec_words = 4 + 2 * cfg->topm;
+    P->up_bytes = gup(sizeof(GxHdr) + (size_t)cfg->slots * sizeof(GxNewDesc), 256);
+    P->down_bytes = gup((size_t)cfg->slots * 4 + (size_t)cfg->slots * P->rec_words * 4, 256);
+    const size_t per = P->up_bytes + P->down_bytes;
+    e = hipHostMalloc((void **)&P->pinned, per * GRING, hipHostMallocDefault);
+    if (e == hipSuccess) e = hipHostMalloc((void **)&P->qstore, (size_t)cfg->max_outstanding * L.row_pitch, hipHostMallocDefault);
+    if (e == hipSuccess) e = hipHostGetDevicePointer((void **)&P->qstore_dev, P->qstore, 0);
+    for (uint32_t i = 0; i < GRING && e == hipSuccess; ++i) {
+        GStep &R = P->ring[i];
+        R.up_host = P->pinned + i * per;
+        R.down_host = R.up_host + P->up_bytes;
+        e = hipHostGetDevicePointer((void **)&R.up_dev, R.up_host, 0);
+        if (e == hipSuccess) e = hipHostGetDevicePointer((void **)&R.down_dev, R.down_host, 0);
+        if (e == hipSuccess) e = hipEventCreateWithFlags(&R.done, hipEventDisableTiming);
+        if (e == hipSuccess) e = hipEventCreateWithFlags(&R.ev0, hipEventDisableSystemFence);
+        if (e == hipSuccess) e = hipEventCreateWithFlags(&R.ev1, hipEventDisableSystemFence);
+    }
+    if (e != hipSuccess) { graph_pool_destroy(P); return tri_fail(TRI_EHIP, "pinned memory / events -> %s", hipGetErrorString(e)); }
+    try {
+        P->tickets.resize(cfg->max_outstanding);
+        for (uint32_t i = cfg->max_outstanding; i-- > 0;) P->free_tickets.push_back(i);
+        for (uint32_t i = cfg->slots; i-- > 0;) P->free_slots.push_back(i);
+        P->slot_ticket.assign(cfg->slots, 0);
+        P->res_ids.resize((size_t)cfg->max_outstanding * cfg->topm);
+        P->res_score.resize((size_t)cfg->max_outstanding * cfg->topm);
+    } catch (const std::bad_alloc &) {
+        graph_pool_destroy(P);
+        return tri_fail(TRI_ENOMEM, "out of host memory");
+    }
+    P->times.row_bytes = L.row_pitch;
+    *out = P;
+    return TRI_OK;
+}
+
+extern "C" int graph_pool_destroy(tri_gpool *P)
+{
+    if (!P) return tri_fail(TRI_EINVAL, "pool is NULL");
+    (void)hipStreamSynchronize(P->stream);
+    for (uint32_t i = 0; i < GRING; ++i) {
+        if (P->ring[i].done) (void)hipEventDestroy(P->ring[i].done);
+        if (P->ring[i].ev0) (void)hipEventDestroy(P->ring[i].ev0);
+        if (P->ring[i].ev1) (void)hipEventDestroy(P->ring[i].ev1);
+    }
+    if (P->pinned) (void)hipHostFree(P->pinned);
+    if (P->qstore) (void)hipHostFree(P->qstore);
+    delete P;
+    return TRI_OK;
+}
+
+extern "C" int graph_submit(tri_gpool *P, const void *vecs, int on_device, uint64_t pitch_bytes, uint32_t n,
+                            const uint32_t *k, const uint32_t *metric, const uint32_t *klass, tri_ticket *out, uint32_t *n_done)
+{
+    if (n_done) *n_done = 0;
+    if (!P || (n && (!vecs || !k || !metric || !out))) return tri_fail(TRI_EINVAL, "NULL argument");
+    const size_t es = P->D.dtype == TRI_F16 ? 2 : 4;
+    if (pitch_bytes < (uint64_t)P->D.dim * es || pitch_bytes % es) return tri_fail(TRI_EINVAL, "pitch_bytes too small or not a multiple of the element size");
+    for (uint32_t i = 0; i < n; ++i) {
+        if (k[i] == 0 || k[i] > P->cfg.topm) return tri_fail(TRI_EINVAL, "k must be 1..topm (query %u has %u)", i, k[i]);
+        if (metric[i] != TRI_L2 && metric[i] != TRI_IP) return tri_fail(TRI_EINVAL, "metric must be TRI_L2 or TRI_IP");
+        if (klass && klass[i] != TRI_CLASS_HIGH && klass[i] != TRI_CLASS_LOW) return tri_fail(TRI_EINVAL, "klass must be TRI_CLASS_HIGH or TRI_CLASS_LOW");
+    }
+    std::lock_guard<std::mutex> lk(P->mu);
+    for (uint32_t i = 0; i < n; ++i) {
+        if (P->free_tickets.empty()) return tri_fail(TRI_EAGAIN, "max_outstanding=%u tickets alive", P->cfg.max_outstanding);
+        const uint32_t ti = P->free_tickets.back();
+        P->free_tickets.pop_back();
+        GTicket &t = P->tickets[ti];
+        t.state = G_PENDING;
+        t.k = k[i]; t.metric = metric[i]; t.klass = klass ? klass[i] : (uint32_t)TRI_CLASS_LOW;
+        const uint8_t *src = (const uint8_t *)vecs + (size_t)i * pitch_bytes;
+        if (on_device) {
+            t.dev_vec = src;
+        } else {
+            memcpy(P->qstore + (size_t)ti * P->D.row_pitch, src, (size_t)P->D.dim * es);
+            t.dev_vec = P->qstore_dev + (size_t)ti * P->D.row_pitch;
+        }
+        P->pending[t.klass].push_back(ti);
+        out[i] = ((uint64_t)t.gen << 32) | ti;
+        if (n_done) *n_done = i + 1;
+    }
+    return TRI_OK;
+}
+
+extern "C" int graph_step(tri_gpool *P, tri_graph_step_stats *st)
+{
+    if (!P) return tri_fail(TRI_EINVAL, "pool is NULL");
+    std::lock_guard<std::mutex> lk(P->mu);
+    GHIP(hipSetDevice(P->device));
+    tri_graph_step_stats stats{};
+    int rc = g_reap(P, false, &stats.finished);
+    if (rc) return rc;
+    // at most `depth` steps in flight: wait for the oldest
+    for (;;) {
+        uint32_t in_flight = 0;
+        GStep *oldest = nullptr;
+        for (uint32_t i = 0; i < GRING; ++i)
+            if (P->ring[i].in_use) {
+                ++in_flight;
+                if (!oldest || P->ring[i].seq < oldest->seq) oldest = &P->ring[i];
+            }
+        if (in_flight < P->depth) break;
+        GHIP(hipEventSynchronize(oldest->done));
+        rc = g_reap(P, false, &stats.finished);
+        if (rc) return rc;
+    }
+    GStep *Rp = nullptr;
+    for (uint32_t i = 0; i < GRING; ++i)
+        if (!P->ring[i].in_use) { Rp = &P->ring[i]; break; }
+    GStep &R = *Rp;
+    // admit: high class first, first-in first-out inside a class
+    GxHdr *hdr = (GxHdr *)R.up_host;
+    GxNewDesc *desc = (GxNewDesc *)(R.up_host + sizeof(GxHdr));
+    uint32_t n_new = 0;
+    for (int klass = 0; klass < 2; ++klass) {
+        std::deque<uint32_t> &Q = P->pending[klass];
+        while (!Q.empty() && !P->free_slots.empty()) {
+            const uint32_t ti = Q.front();
+            Q.pop_front();
+            const uint32_t slot = P->free_slots.back();
+            P->free_slots.pop_back();
+            GTicket &t = P->tickets[ti];
+            t.state = G_RUNNING;
+            t.slot = slot;
+            P->slot_ticket[slot] = ti;
+            desc[n_new++] = GxNewDesc{slot, t.k, t.metric, 0u, (uint64_t)(uintptr_t)t.dev_vec, 0ull};
+            ++P->n_running;
+        }
+    }
+    stats.step = P->step_seq;
+    stats.admitted = n_new;
+    stats.running = P->n_running;
+    stats.pending = (uint32_t)(P->pending[0].size() + P->pending[1].size());
+    if (P->n_running == 0) {
+        if (st) *st = stats;
+        return TRI_OK;
+    }
+    hdr->n16 = (uint32_t)((sizeof(GxHdr) + (size_t)n_new * sizeof(GxNewDesc) + 15) / 16);
+    hdr->n_new = n_new;
+    memset(R.down_host, 0, (size_t)P->cfg.slots * 4);   // (this entry's previous step has been collected: the block is ours)
+    hipStream_t s = P->stream;
+    const GxDev &D = P->D;
+    const bool prof = (P->cfg.flags & TRI_FLAG_PROFILE) != 0;
+    hipLaunchKernelGGL(gx_pull_kernel, dim3((hdr->n16 + 255) / 256), dim3(256), 0, s, (uint4 *)D.upload, (const uint4 *)R.up_dev);
+    if (n_new) hipLaunchKernelGGL(gx_admit_kernel, dim3(n_new), dim3(GX_THREADS), 0, s, D);
+    hipLaunchKernelGGL(gx_extend_kernel, dim3(D.S), dim3(GX_THREADS), 0, s, D);
+    GHIP(hipGetLastError());
+    if (prof) GHIP(hipEventRecord(R.ev0, s));
+    GHIP(D.dtype == TRI_F16 ? g_launch_distance<TRI_F16>(P) : g_launch_distance<TRI_F32>(P));
+    if (prof) GHIP(hipEventRecord(R.ev1, s));
+    hipLaunchKernelGGL(gx_merge_kernel, dim3(D.S), dim3(GX_THREADS), 0, s, D, (uint32_t *)R.down_dev,
+                       (uint32_t *)R.down_dev + D.S, P->rec_words);
+    GHIP(hipGetLastError());
+    GHIP(hipEventRecord(R.done, s));
+    R.in_use = true;
+    R.profiled = prof;
+    R.seq = P->step_seq++;
+    if (st) *st = stats;
+    return TRI_OK;
+}
+
+extern "C" int graph_poll(tri_gpool *P, const tri_ticket *tk, uint32_t n, uint32_t stride, uint32_t *n_out, int64_t *ids,
+                          float *dist, uint32_t *iters, uint32_t *evals, int *status)
+{
+    if (!P || (n && (!tk || !n_out || !ids || !dist || !status))) return tri_fail(TRI_EINVAL, "NULL argument");
+    std::lock_guard<std::mutex> lk(P->mu);
+    int rc = g_reap(P, false, nullptr);
+    if (rc) return rc;
+    int delivered = 0;
+    const uint32_t M = P->cfg.topm;
+    for (uint32_t i = 0; i < n; ++i) {
+        const uint32_t ti = (uint32_t)(tk[i] & 0xFFFFFFFFu), gen = (uint32_t)(tk[i] >> 32);
+        if (ti >= P->tickets.size() || P->tickets[ti].gen != gen || P->tickets[ti].state == G_FREE) { status[i] = TRI_ENOENT; continue; }
+        GTicket &t = P->tickets[ti];
+        if (t.state != G_DONE) { status[i] = TRI_EAGAIN; continue; }
+        if (stride < t.k) return tri_fail(TRI_EINVAL, "stride %u is smaller than ticket %u's k = %u", stride, i, t.k);
+        int64_t *oi = ids + (size_t)i * stride;
+        float *od = dist + (size_t)i * stride;
+        for (uint32_t j = 0; j < t.n_out; ++j) { oi[j] = (int64_t)P->res_ids[(size_t)ti * M + j]; od[j] = P->res_score[(size_t)ti * M + j]; }
+        const float pad = t.metric == TRI_L2 ? __builtin_inff() : -__builtin_inff();
+        for (uint32_t j = t.n_out; j < t.k; ++j) { oi[j] = -1; od[j] = pad; }
+        n_out[i] = t.n_out;
+        if (iters) iters[i] = t.iters;
+        if (evals) evals[i] = t.evals;
+        status[i] = TRI_OK;
+        t.state = G_FREE;
+        ++t.gen;
+        P->free_tickets.push_back(ti);
+        ++delivered;
+    }
+    return delivered;
+}
+
+extern "C" int graph_sync(tri_gpool *P)
+{
+    if (!P) return tri_fail(TRI_EINVAL, "pool is NULL");
+    std::lock_guard<std::mutex> lk(P->mu);
+    GHIP(hipSetDevice(P->device));
+    return g_reap(P, true, nullptr);
+}
+
+extern "C" int graph_kernel_times(tri_gpool *P, tri_graph_times *out, int reset)
+{
+    if (!P || !out) return tri_fail(TRI_EINVAL, "NULL argument");
+    std::lock_guard<std::mutex> lk(P->mu);
+    *out = P->times;
+    if (reset) { const uint32_t rb = P->times.row_bytes; P->times = tri_graph_times{}; P->times.row_bytes = rb; }
+    return TRI_OK;
+}

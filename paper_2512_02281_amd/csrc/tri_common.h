@@ -178,6 +178,9 @@ struct TriLaunchCtx {
     uint32_t S, W, kmax, nprobe_max, max_total_lists, slot_row_bytes, n_cu;
 };
 
+// Record the thread's last error text (what tri_last_error() returns) and hand back `code`.
+int tri_fail(int code, const char *fmt, ...) __attribute__((format(printf, 2, 3)));
+
 // ---- launchers (each returns hipGetLastError() of its launches) -----------------------------
 // The kernels of a step read what the step holds from the TriStepHdr at the head of ws.upload; the
 // grid_* arguments only size the launches: at least what the step needs (its exact counts, or the
