@@ -41,10 +41,15 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=100)
     ap.add_argument("--warmup", type=int, default=10)
-    ap.add_argument("--workload", default="config4", choices=["config4", "config2", "config1", "config3"])
+    ap.add_argument("--workload", default="config4", choices=["config4", "config2", "config1", "config3", "graph"])
+    ap.add_argument("--graph-n", type=int, default=1_000_000, help="graph workload: database rows")
+    ap.add_argument("--graph-slots", type=int, default=8192, help="graph workload: requests advanced per step")
+    ap.add_argument("--graph-topm", type=int, default=128, help="graph workload: length of a request's candidate list")
+    ap.add_argument("--graph-parents", type=int, default=4, help="graph workload: parents expanded per extend")
+    ap.add_argument("--graph-seeds", type=int, default=64, help="graph workload: entry points")
     ap.add_argument("--stream-queries", type=int, default=100_000, help="config3: queries in the stream")
     ap.add_argument("--cpu-sample", type=int, default=-1, help="queries timed on the CPU oracle (0 = skip)")
-    ap.add_argument("--recall-sample", type=int, default=64)
+    ap.add_argument("--recall-sample", type=int, default=64, help="queries checked against exact search (graph workload: 4 x as many)")
     ap.add_argument("--host-queries", action="store_true",
                     help="submit the query vectors from host memory (adds their PCIe transfer to every step; "
                          "a side measurement, never the headline value)")
@@ -68,6 +73,8 @@ def main():
     if not torch.cuda.is_available():
         print("bench.py: no GPU", file=sys.stderr)
         sys.exit(3)
+    if args.workload == "graph":
+        return graph_bench(args, tri, torch)
     number = int(args.workload[-1])
     if number == 3:
         return stream_bench(args, tri, workloads, torch)
@@ -389,6 +396,114 @@ def stream_bench(args, tri, workloads, torch):
                      "avg_launch_ms": round(scan_ms, 4), "algorithmic_bytes_per_launch": int(unique_b),
                      "note": "at most 1.84 GB of lists per step, smaller than the 256 MB cache only in part: cache-assisted, not an HBM figure"},
         "stream": runs,
+        "cpu_baseline": cpu,
+        "wall_s_total": round(time.time() - t_start, 1),
+    }
+    pool.close()
+    print(json.dumps(result), flush=True)
+
+
+def graph_bench(args, tri, torch):
+    """The paper's own engine (Sec. 3.2) on a config-2-sized corpus: n x 768 fp16 unit-norm points near a
+    12-dimensional subspace, inner product, a degree-32 neighbour graph (24 nearest + 8 random rows), 64
+    entry points, topM 64, 4 parents per extend, at most 64 extends, k 10.  One bench step = one batch of
+    4 * slots device-resident queries from submission to the last result."""
+    import graph_inputs
+    from paper_2512_02281_amd import graph as tg
+    t_start = time.time()
+    n, dim, latent, D, n_rand, M, p, iters, k = args.graph_n, 768, 12, 32, 8, args.graph_topm, args.graph_parents, 64, 10
+    S = args.graph_slots
+    Q = 4 * S
+    log(f"workload graph: generating {n} x {dim} fp16 and its degree-{D} neighbour list (untimed)")
+    X, Z = graph_inputs.make_points(n, dim, latent, np.float16, graph_inputs.SEED_POINTS, device="cuda")
+    Qv, _ = graph_inputs.make_points(Q, dim, latent, np.float16, graph_inputs.SEED_QUERIES, device="cuda")
+    G = graph_inputs.make_graph(Z, D, n_rand, graph_inputs.SEED_EDGES, block=1024).to(torch.int32)
+    seeds = graph_inputs.entry_points(n, args.graph_seeds)
+    torch.cuda.synchronize()
+    log(f"inputs ready after {time.time() - t_start:.1f} s")
+    pool = tg.GraphPool(X, G, seeds, tri.TRI_F16, slots=S, topm=M, parents=p, max_iters=iters, max_outstanding=2 * Q,
+                        depth=2, flags=tri.TRI_FLAG_PROFILE, own_stream=True)
+    kk = np.full(Q, k, dtype=np.uint32)
+    mm = np.full(Q, tri.TRI_IP, dtype=np.uint32)
+
+    def one_batch():
+        return pool.run_all(Qv, kk, mm)
+
+    if args.copy_calibration_mib:
+        src = torch.ones(args.copy_calibration_mib << 18, dtype=torch.float32, device="cuda")
+        dst = torch.empty_like(src)
+        dst.copy_(src)                      # reads and writes copy_calibration_mib MiB each
+        torch.cuda.synchronize()
+        del src, dst
+    log("settling and warm-up")
+    t0 = time.perf_counter()
+    while time.perf_counter() - t0 < 0.6:
+        one_batch()
+    for _ in range(args.warmup):
+        one_batch()
+    pool.kernel_times(reset=True)
+    torch.cuda.synchronize()
+    log(f"timing {args.steps} batches of {Q} queries")
+    t0 = time.perf_counter()
+    launches = 0
+    for _ in range(args.steps):
+        ids, dist, n_out, it, ev, steps = one_batch()
+        launches += steps
+    torch.cuda.synchronize()
+    total_s = time.perf_counter() - t0
+    kt = pool.kernel_times()
+    qps = Q * args.steps / total_s
+    dist_ms = kt.distance_ms / max(kt.steps, 1)
+    bytes_per_launch = kt.tasks * kt.row_bytes / max(kt.steps, 1)
+    achieved = bytes_per_launch / (dist_ms * 1e-3) / 1e9 if dist_ms > 0 else 0.0
+    log(f"{total_s * 1e3 / args.steps:.3f} ms/batch, {qps:.0f} q/s; {launches / args.steps:.1f} extend steps per batch, "
+        f"{total_s * 1e6 / launches:.1f} us per step; distance kernel {dist_ms * 1e3:.1f} us/launch for "
+        f"{kt.tasks / max(kt.steps, 1):.0f} rows of {kt.row_bytes} B -> {achieved:.0f} GB/s; mean extends {it.mean():.1f}, "
+        f"mean distance evaluations {ev.mean():.0f} per query")
+    recall = None
+    if args.recall_sample:
+        rs = np.random.default_rng(77).choice(Q, size=min(4 * args.recall_sample, Q), replace=False)
+        hits = 0
+        for qi in rs:
+            top = torch.topk((X @ Qv[int(qi)]).float(), k).indices.cpu().numpy().tolist()
+            hits += len(set(top) & set(ids[qi, :k].tolist()))
+        recall = hits / (k * rs.size)
+        log(f"recall@{k} on {rs.size} queries: {recall:.4f}")
+    cpu = None
+    n_cpu = args.cpu_sample if args.cpu_sample >= 0 else 256
+    if n_cpu:
+        from oracle import graph_search as gs
+        log("CPU oracle (one request at a time, one core) on a sample of the batch")
+        Xh, Gh = X.cpu().numpy(), G.cpu().numpy().astype(np.uint32)
+        sel = np.arange(0, Q, max(1, Q // n_cpu))[:n_cpu]
+        Qh = Qv.cpu().numpy()[sel]
+        tc0 = time.perf_counter()
+        same = 0
+        for j, qi in enumerate(sel):
+            r = gs.search(Xh, Gh, seeds, Qh[j], k, M, p, iters, gs.METRIC_IP)
+            same += np.array_equal(r["ids"], ids[qi, :k])
+        tc = time.perf_counter() - tc0
+        cpu = {"value": round(sel.size / tc, 3), "unit": "queries/s", "cores": 1, "kind": "oracle",
+               "sample": f"{sel.size} queries of the same batch (every {max(1, Q // n_cpu)}-th), {tc:.1f} s of wall time; "
+                         f"{same} of them returned exactly the GPU's ids"}
+        log(f"cpu oracle: {cpu}")
+    result = {
+        "metric": "queries/sec at recall@k>=0.9 (1 GPU) + list-scan HBM GB/s as % of peak",
+        "value": round(qps, 1), "unit": "queries/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(total_s * 1e3 / args.steps, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f16", "data": "synthetic",
+        "config": {"workload": f"graph engine (paper Sec. 3.2): {n} x {dim} fp16 near a {latent}-dim subspace, inner product, "
+                               f"degree {D} ({D - n_rand} nearest + {n_rand} random), {seeds.size} entry points, topM {M}, {p} parents per "
+                               f"extend, at most {iters} extends, k {k}; {S} slots, batches of {Q} queries",
+                   "queries_per_step": Q, "extend_steps_per_batch": round(launches / args.steps, 1),
+                   "us_per_extend_step": round(total_s * 1e6 / launches, 2),
+                   "mean_extends_per_query": round(float(it.mean()), 2), "mean_evaluations_per_query": round(float(ev.mean()), 1),
+                   "recall_at_k": None if recall is None else round(recall, 4), "query_vectors": "device-resident"},
+        "roofline": {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": None, "kernel": "gx_distance_kernel",
+                     "avg_launch_ms": round(dist_ms, 5), "algorithmic_bytes_per_launch": int(bytes_per_launch),
+                     "rows_per_launch": int(kt.tasks / max(kt.steps, 1)), "row_bytes": int(kt.row_bytes),
+                     "note": "gathered rows: every distance task reads one 1536-byte row once"},
         "cpu_baseline": cpu,
         "wall_s_total": round(time.time() - t_start, 1),
     }

@@ -1,15 +1,15 @@
 // The paper's own engine (Sec. 3.2): continuous batching of best-first searches over a fixed-degree
 // neighbour graph, one "extend" of every running request per step.  Per request and on the device: a
 // candidate list topM (sorted composites of score key, id and an "expanded" mark), a visited bit table
-// (one bit per database row, so "first seen" is exact), its query row.  A step is four fixed-shape
+// (one bit per database row, so "first seen" is exact), its query row.  A step is two fixed-shape
 // launches over all S slots -- idle slots leave at once, which is the masked padding of the paper's
 // fixed-shape task array:
-//   extend   : up to p non-expanded parents of topM, their D neighbours, visited filter -> compacted
-//              distance tasks of the slot (at most p * D);
-//   distance : every task = one gathered row against the slot's query, 16 lanes per task;
-//   merge    : tasks' (score, id) + topM -> new topM by rank counting; stop rule; finished requests write
-//              their record into the step's pinned result block.
-// Newly admitted requests take the place of `extend` with their entry points as tasks.
+//   distance       : every task of every slot = one gathered row against the slot's query, 16 lanes per task;
+//   merge + extend : tasks' (score, id) + topM -> new topM; stop rule; finished requests write their
+//                    record into the step's pinned result block; the others select up to p non-expanded
+//                    parents of the new topM, read their D neighbours, filter by visited and leave the
+//                    survivors (at most p * D) as the slot's distance tasks of the next step.
+// A newly admitted request enters with its entry points as tasks (admit kernel, before the distance launch).
 #include "../../include/trinity_graph.h"
 #include "tri_common.h"
 
@@ -162,48 +162,6 @@ __global__ __launch_bounds__(GX_THREADS) void gx_admit_kernel(GxDev D)
     }
 }
 
-// ------------------------------------------------------------------------------------------ extend
-// One workgroup per slot.  Thread i looks at topM entry i: the first p non-expanded ones (in topM's order)
-// become parents and are marked; thread t then takes neighbour t % D of parent t / D through the visited
-// filter; the survivors are compacted into the slot's task list.
-__global__ __launch_bounds__(GX_THREADS) void gx_extend_kernel(GxDev D)
-{
-    __shared__ uint32_t wave_cnt[4];
-    __shared__ uint32_t parent[TRI_GRAPH_TASK_LIMIT];
-    const uint32_t s = blockIdx.x, tid = threadIdx.x;
-    GxMeta *m = D.meta + s;
-    if (m->state != 1u || m->fresh) return;               // (idle: masked; fresh: its tasks are the entry points)
-    unsigned long long e = ~0ull;
-    if (tid < D.M) e = D.topm[(size_t)s * D.M + tid];
-    const bool unexp = e != ~0ull && !(e & 1ull);
-    uint32_t total;
-    const uint32_t rank = gx_block_rank(unexp, wave_cnt, &total);
-    if (unexp && rank < D.p) {
-        parent[rank] = (uint32_t)(e & 0xFFFFFFFFull) >> 1;
-        D.topm[(size_t)s * D.M + tid] = e | 1ull;
-    }
-    const uint32_t n_par = total < D.p ? total : D.p;
-    __syncthreads();
-    uint32_t v = TRI_GRAPH_PAD;
-    const uint32_t par = tid / D.degree, j = tid % D.degree;
-    if (par < n_par) {
-        const uint32_t c = D.graph[(size_t)parent[par] * D.degree + j];
-        if (c < D.n) {
-            const uint32_t bit = 1u << (c & 31);
-            const uint32_t old = atomicOr(&D.visited[(size_t)s * D.vwords + (c >> 5)], bit);
-            if (!(old & bit)) v = c;
-        }
-    }
-    uint32_t n_tasks;
-    const uint32_t pos = gx_block_rank(v != TRI_GRAPH_PAD, wave_cnt, &n_tasks);
-    if (v != TRI_GRAPH_PAD) D.tasks[(size_t)s * D.T + pos] = v;
-    if (tid == 0) {
-        m->n_par = n_par;
-        m->n_tasks = n_tasks;
-        m->evals += n_tasks;
-    }
-}
-
 // ------------------------------------------------------------------------------------------ distance
 // One workgroup per slot, the slot's query row in LDS; a team of 16 lanes per task reads the task's row
 // in 256-byte pieces (16 bytes per lane, consecutive lanes consecutive addresses: two full 128-byte
@@ -259,78 +217,130 @@ __global__ __launch_bounds__(GX_THREADS) void gx_distance_kernel(GxDev D)
     }
 }
 
-// ------------------------------------------------------------------------------------------ merge
-// One workgroup per slot: the step's (score, id) pairs and topM, as composites (key << 32 | id << 1 |
-// expanded; ids are unique: a row is scored at most once per request), are ranked by counting; the first
-// M form the new topM.  topM changed iff one of the new pairs ranks among the first M.
-__global__ __launch_bounds__(GX_THREADS) void gx_merge_kernel(GxDev D, uint32_t *__restrict__ done, uint32_t *__restrict__ rec_base,
-                                                              uint32_t rec_words)
+// ------------------------------------------------------------------------------------------ merge + extend
+// One workgroup per slot.
+//  merge : the step's (score, id) pairs join topM.  Elements are composites (key << 32 | id << 1 | expanded;
+//          ids are unique: a row is scored at most once per request).  topM is sorted already, so only the
+//          new pairs are sorted (rank counting among themselves); the final rank of a new pair is its rank
+//          among the new ones plus the number of topM entries below it (binary search), that of a topM
+//          entry its index plus the number of new pairs below it.  The first M form the new topM; it
+//          changed iff a new pair ranks among them.
+//  stop  : by the paper's rule (topM unchanged), the extend budget, or no parent left.
+//  extend: a request that goes on selects its next parents at once -- thread i looks at entry i of the new
+//          topM: the first p non-expanded ones (in topM's order) become parents and are marked; thread t
+//          takes neighbour t % D of parent t / D through the visited filter; the survivors, compacted, are
+//          the slot's distance tasks of the next step.
+__device__ __forceinline__ uint32_t gx_count_below(const unsigned long long *a, uint32_t n, unsigned long long x)
 {
-    __shared__ unsigned long long el[TRI_GRAPH_TOPM_LIMIT + TRI_GRAPH_TASK_LIMIT];
+    uint32_t lo = 0, hi = n;                 // a ascending: number of entries < x
+    while (lo < hi) {
+        const uint32_t mid = (lo + hi) >> 1;
+        if (a[mid] < x) lo = mid + 1; else hi = mid;
+    }
+    return lo;
+}
+
+__global__ __launch_bounds__(GX_THREADS) void gx_merge_extend_kernel(GxDev D, uint32_t *__restrict__ done,
+                                                                     uint32_t *__restrict__ rec_base, uint32_t rec_words)
+{
+    __shared__ unsigned long long old[TRI_GRAPH_TOPM_LIMIT];
+    __shared__ unsigned long long nw[TRI_GRAPH_TASK_LIMIT];
+    __shared__ unsigned long long snew[TRI_GRAPH_TASK_LIMIT];
     __shared__ unsigned long long out[TRI_GRAPH_TOPM_LIMIT];
-    __shared__ uint32_t changed;
-    __shared__ uint32_t n_sh;
+    __shared__ uint32_t parent[TRI_GRAPH_TASK_LIMIT];
+    __shared__ uint32_t wave_cnt[4];
+    __shared__ uint32_t changed, n_sh;
     const uint32_t s = blockIdx.x, tid = threadIdx.x;
     GxMeta *mp = D.meta + s;
     const GxMeta m = *mp;
-    if (m.state != 1u) return;
+    if (m.state != 1u) return;                                    // (idle slot: masked)
     const uint32_t desc = m.metric == TRI_IP;
-    const uint32_t nt = m.n_tasks, n_el = D.M + nt;
+    const uint32_t nt = m.n_tasks, M = D.M;
     if (tid == 0) { changed = 0; n_sh = 0; }
-    for (uint32_t i = tid; i < n_el; i += GX_THREADS) {
-        unsigned long long e;
-        if (i < D.M) e = D.topm[(size_t)s * D.M + i];
-        else {
-            const uint32_t t = i - D.M;
-            e = ((unsigned long long)gx_key(D.tdist[(size_t)s * D.T + t], desc) << 32) |
-                ((unsigned long long)D.tasks[(size_t)s * D.T + t] << 1);
-        }
-        el[i] = e;
-    }
-    for (uint32_t i = tid; i < D.M; i += GX_THREADS) out[i] = ~0ull;
+    unsigned long long mine = ~0ull;                              // this thread's new pair (T <= 256 = threads)
+    if (tid < nt)
+        mine = ((unsigned long long)gx_key(D.tdist[(size_t)s * D.T + tid], desc) << 32) |
+               ((unsigned long long)D.tasks[(size_t)s * D.T + tid] << 1);
+    nw[tid] = mine;
+    if (tid < M) { old[tid] = D.topm[(size_t)s * M + tid]; out[tid] = ~0ull; }
     __syncthreads();
-    for (uint32_t i = tid; i < n_el; i += GX_THREADS) {
-        const unsigned long long e = el[i];
-        if (e == ~0ull) continue;                       // empty topM entries stay at the end
-        uint32_t r = 0;
-        for (uint32_t j = 0; j < n_el; ++j) r += el[j] < e;
-        if (r < D.M) {
-            out[r] = e;
-            if (i >= D.M) changed = 1u;                 // (benign race: every writer stores 1)
+    uint32_t r_new = 0;
+    if (tid < nt)
+        for (uint32_t j = 0; j < nt; ++j) r_new += nw[j] < mine;
+    if (tid < nt) snew[r_new] = mine;
+    __syncthreads();
+    if (tid < nt) {
+        const uint32_t r = r_new + gx_count_below(old, M, mine);
+        if (r < M) { out[r] = mine; changed = 1u; }               // (benign race: every writer stores 1)
+    }
+    if (tid < M) {
+        const unsigned long long e = old[tid];
+        if (e != ~0ull) {                                          // empty entries stay at the end
+            const uint32_t r = tid + gx_count_below(snew, nt, e);
+            if (r < M) out[r] = e;
         }
     }
     __syncthreads();
-    for (uint32_t i = tid; i < D.M; i += GX_THREADS) D.topm[(size_t)s * D.M + i] = out[i];
     // stop rule
     bool finish;
     uint32_t iters = m.iters;
     if (m.fresh) finish = D.max_iters == 0;
-    else if (m.n_par == 0) finish = true;               // no parent left: not an extend
     else {
-        iters += 1;
+        iters += 1;                                                // (a running slot reaches this kernel only with parents)
         finish = !changed || iters >= D.max_iters;
     }
+    uint32_t n_par = 0, n_tasks = 0;
+    if (!finish) {
+        const unsigned long long e = tid < M ? out[tid] : ~0ull;
+        const bool unexp = e != ~0ull && !(e & 1ull);
+        uint32_t total;
+        const uint32_t rank = gx_block_rank(unexp, wave_cnt, &total);
+        if (unexp && rank < D.p) {
+            parent[rank] = (uint32_t)(e & 0xFFFFFFFFull) >> 1;
+            out[tid] = e | 1ull;
+        }
+        n_par = total < D.p ? total : D.p;
+        if (n_par == 0) finish = true;                             // nothing left to expand: not an extend
+        __syncthreads();
+    }
+    if (!finish) {
+        uint32_t v = TRI_GRAPH_PAD;
+        const uint32_t par = tid / D.degree, j = tid % D.degree;
+        if (par < n_par) {
+            const uint32_t c = D.graph[(size_t)parent[par] * D.degree + j];
+            if (c < D.n) {
+                const uint32_t bit = 1u << (c & 31);
+                const uint32_t was = atomicOr(&D.visited[(size_t)s * D.vwords + (c >> 5)], bit);
+                if (!(was & bit)) v = c;
+            }
+        }
+        const uint32_t pos = gx_block_rank(v != TRI_GRAPH_PAD, wave_cnt, &n_tasks);
+        if (v != TRI_GRAPH_PAD) D.tasks[(size_t)s * D.T + pos] = v;
+    }
+    if (tid < M) D.topm[(size_t)s * M + tid] = out[tid];
     if (finish) {
         uint32_t *rec = rec_base + (size_t)s * rec_words;
         uint32_t n_valid = 0;
-        for (uint32_t i = tid; i < D.M; i += GX_THREADS) {
-            const unsigned long long e = out[i];
-            const bool ok = e != ~0ull && i < m.k;
-            rec[4 + i] = ok ? (uint32_t)(e & 0xFFFFFFFFull) >> 1 : 0xFFFFFFFFu;
-            rec[4 + D.M + i] = ok ? __float_as_uint(gx_unkey((uint32_t)(e >> 32), desc)) : 0u;
-            n_valid += ok;
+        if (tid < M) {
+            const unsigned long long e = out[tid];
+            const bool ok = e != ~0ull && tid < m.k;
+            rec[4 + tid] = ok ? (uint32_t)(e & 0xFFFFFFFFull) >> 1 : 0xFFFFFFFFu;
+            rec[4 + M + tid] = ok ? __float_as_uint(gx_unkey((uint32_t)(e >> 32), desc)) : 0u;
+            n_valid = ok;
         }
-        if (n_valid) atomicAdd(&n_sh, n_valid);          // n = valid entries among the first k
+        if (n_valid) atomicAdd(&n_sh, n_valid);                   // n = valid entries among the first k
         __syncthreads();
         if (tid == 0) {
             rec[0] = n_sh; rec[1] = iters; rec[2] = m.evals; rec[3] = 0u;
             mp->state = 0u;
-            __threadfence_system();                       // the record before the mark the host looks for
-            done[s] = 1u;
+            done[s] = 1u;                                          // (the host looks only after the step has completed)
         }
     } else if (tid == 0) {
         mp->iters = iters;
         mp->fresh = 0u;
+        mp->n_par = n_par;
+        mp->n_tasks = n_tasks;
+        mp->evals = m.evals + n_tasks;
     }
 }
 
@@ -714,12 +724,11 @@ extern "C" int graph_step(tri_gpool *P, tri_graph_step_stats *st)
     const bool prof = (P->cfg.flags & TRI_FLAG_PROFILE) != 0;
     hipLaunchKernelGGL(gx_pull_kernel, dim3((hdr->n16 + 255) / 256), dim3(256), 0, s, (uint4 *)D.upload, (const uint4 *)R.up_dev);
     if (n_new) hipLaunchKernelGGL(gx_admit_kernel, dim3(n_new), dim3(GX_THREADS), 0, s, D);
-    hipLaunchKernelGGL(gx_extend_kernel, dim3(D.S), dim3(GX_THREADS), 0, s, D);
     GHIP(hipGetLastError());
     if (prof) GHIP(hipEventRecord(R.ev0, s));
     GHIP(D.dtype == TRI_F16 ? g_launch_distance<TRI_F16>(P) : g_launch_distance<TRI_F32>(P));
     if (prof) GHIP(hipEventRecord(R.ev1, s));
-    hipLaunchKernelGGL(gx_merge_kernel, dim3(D.S), dim3(GX_THREADS), 0, s, D, (uint32_t *)R.down_dev,
+    hipLaunchKernelGGL(gx_merge_extend_kernel, dim3(D.S), dim3(GX_THREADS), 0, s, D, (uint32_t *)R.down_dev,
                        (uint32_t *)R.down_dev + D.S, P->rec_words);
     GHIP(hipGetLastError());
     GHIP(hipEventRecord(R.done, s));

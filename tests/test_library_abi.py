@@ -23,8 +23,8 @@ def tri():
     return tri
 
 
-def _declared_functions():
-    text = open(HEADER).read()
+def _declared_functions(header=HEADER):
+    text = open(header).read()
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
     names = re.findall(r"^\s*(?:const\s+char\s*\*\s*|int\s+)(\w+)\s*\(", text, flags=re.M)
     return sorted(set(names))
@@ -163,6 +163,46 @@ def test_slack_order_properties(tri):
         m = int(rng.integers(0, n + 1))                     # only the m most urgent in slack order, the rest by arrival
         assert tri.tri_policy_slack_order(d, e, now, step, m).tolist() == full[:m] + sorted(full[m:])
     assert tri.tri_policy_slack_order(np.zeros(0, np.int64), np.zeros(0, np.uint32), now, step).shape == (0,)
+
+
+def test_graph_header_exports_layouts_and_validation(tri):
+    """include/trinity_graph.h: every declared function is exported and bound, the structs have the layout the
+    binding assumes, and the size query validates its arguments (no GPU needed)."""
+    from paper_2512_02281_amd import graph as tg
+    header = os.path.join(ROOT, "include", "trinity_graph.h")
+    declared = _declared_functions(header)
+    assert sorted(tg.GRAPH_EXPORTS) == declared
+    lib = ctypes.CDLL(tri.LIB_PATH)
+    for name in declared:
+        assert hasattr(lib, name), f"{name} is declared in the header but not exported"
+    prog = r'''
+#include <stdio.h>
+#include <stddef.h>
+#include "trinity_graph.h"
+int main(void) {
+  printf("%zu %zu %zu %zu %zu %u %u\n", sizeof(tri_graph_cfg), sizeof(tri_graph_step_stats), sizeof(tri_graph_times),
+         offsetof(tri_graph_cfg, hip_stream), offsetof(tri_graph_times, row_bytes), TRI_GRAPH_TOPM_LIMIT, TRI_GRAPH_TASK_LIMIT);
+  return 0;
+}'''
+    with tempfile.TemporaryDirectory() as tmp:
+        src, exe = os.path.join(tmp, "a.c"), os.path.join(tmp, "a.out")
+        open(src, "w").write(prog)
+        subprocess.check_call(["gcc", "-std=c99", "-I", os.path.join(ROOT, "include"), "-o", exe, src])
+        out = [int(v) for v in subprocess.check_output([exe]).decode().split()]
+    assert out == [ctypes.sizeof(tg.tri_graph_cfg), ctypes.sizeof(tg.tri_graph_step_stats), ctypes.sizeof(tg.tri_graph_times),
+                   tg.tri_graph_cfg.hip_stream.offset, tg.tri_graph_times.row_bytes.offset, tg.TRI_GRAPH_TOPM_LIMIT,
+                   tg.TRI_GRAPH_TASK_LIMIT]
+    size = ctypes.c_size_t(0)
+    ok = tg.tri_graph_cfg(64, 64, 4, 32, 256, 0, 0, 0, None)
+    assert lib.graph_pool_bytes(ctypes.byref(ok), 100000, 768, 32, tri.TRI_F16, ctypes.byref(size)) == tri.TRI_OK
+    # rows (padded to 256 B), |x|^2, neighbour list and 64 visited tables are in there
+    assert size.value >= 100000 * (1536 + 4 + 32 * 4) + 64 * (100000 // 8)
+    for bad in (tg.tri_graph_cfg(0, 64, 4, 32, 256, 0, 0, 0, None), tg.tri_graph_cfg(64, 257, 4, 32, 256, 0, 0, 0, None),
+                tg.tri_graph_cfg(64, 64, 9, 32, 256, 0, 0, 0, None), tg.tri_graph_cfg(64, 64, 4, 32, 32, 0, 0, 0, None),
+                tg.tri_graph_cfg(64, 64, 4, 32, 256, 5, 0, 0, None)):
+        assert lib.graph_pool_bytes(ctypes.byref(bad), 100000, 768, 32, tri.TRI_F16, ctypes.byref(size)) == tri.TRI_EINVAL
+    assert lib.graph_pool_bytes(ctypes.byref(ok), 0, 768, 32, tri.TRI_F16, ctypes.byref(size)) == tri.TRI_EINVAL
+    assert lib.graph_pool_bytes(ctypes.byref(ok), 1000, 5000, 32, tri.TRI_F16, ctypes.byref(size)) == tri.TRI_EINVAL
 
 
 def test_feedback_period_matches_the_oracle_rule(tri):
