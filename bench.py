@@ -46,6 +46,7 @@ def main():
     ap.add_argument("--graph-slots", type=int, default=8192, help="graph workload: requests advanced per step")
     ap.add_argument("--graph-topm", type=int, default=128, help="graph workload: length of a request's candidate list")
     ap.add_argument("--graph-parents", type=int, default=4, help="graph workload: parents expanded per extend")
+    ap.add_argument("--graph-groups", type=int, default=2, help="graph workload: slot groups stepped in turn (1..4)")
     ap.add_argument("--graph-seeds", type=int, default=64, help="graph workload: entry points")
     ap.add_argument("--stream-queries", type=int, default=100_000, help="config3: queries in the stream")
     ap.add_argument("--cpu-sample", type=int, default=-1, help="queries timed on the CPU oracle (0 = skip)")
@@ -422,7 +423,7 @@ def graph_bench(args, tri, torch):
     torch.cuda.synchronize()
     log(f"inputs ready after {time.time() - t_start:.1f} s")
     pool = tg.GraphPool(X, G, seeds, tri.TRI_F16, slots=S, topm=M, parents=p, max_iters=iters, max_outstanding=2 * Q,
-                        depth=2, flags=tri.TRI_FLAG_PROFILE, own_stream=True)
+                        groups=args.graph_groups, flags=tri.TRI_FLAG_PROFILE, own_stream=True)
     kk = np.full(Q, k, dtype=np.uint32)
     mm = np.full(Q, tri.TRI_IP, dtype=np.uint32)
 

@@ -46,7 +46,12 @@ typedef struct {
     uint32_t parents;          /* p: parents expanded per request and extend; p * degree <= TRI_GRAPH_TASK_LIMIT */
     uint32_t max_iters;        /* a request stops after this many extends at the latest                 */
     uint32_t max_outstanding;  /* tickets alive at once (pending + running + finished, unpolled), >= slots */
-    uint32_t depth;            /* steps in flight before graph_step waits for the oldest: 1..4 (0 = 2)   */
+    uint32_t groups;           /* the slots are split into this many groups (slot s in group s mod groups); a
+                                  call of graph_step advances ONE group, in turn, each on a stream of its
+                                  own, with at most one step per group in flight -- so the latency-bound
+                                  merge of one group runs beside the bandwidth-bound distance launch of
+                                  another, and a step is enqueued knowing which of its group's slots the
+                                  previous one freed: 1..4 (0 = 2)                                      */
     uint32_t flags;            /* TRI_FLAG_PROFILE: bracket the distance kernel with HIP events          */
     uint32_t pad_;
     void *hip_stream;          /* stream all work is enqueued on (hipStream_t); NULL = default stream    */
@@ -86,9 +91,10 @@ typedef struct {
     uint32_t pending;      /* queries still waiting for a slot                                          */
 } tri_graph_step_stats;
 
-/* One step: collect the results of completed steps (their slots become free), admit waiting queries
- * into free slots (high class first, first-in first-out inside a class), enqueue one extend of every
- * running request.  Only enqueues GPU work.  A call with nothing running and nothing waiting is a no-op. */
+/* One step of the next group of slots (see tri_graph_cfg.groups): wait for that group's previous step and
+ * collect its results (their slots become free), admit waiting queries into the group's free slots (high
+ * class first, first-in first-out inside a class), enqueue one extend of every running request of the
+ * group.  Only enqueues GPU work.  A call with nothing running in the group and nothing to admit is a no-op. */
 int graph_step(tri_gpool *pool, tri_graph_step_stats *stats /*[host] out or NULL*/);
 
 /* Results of n tickets, as search_poll_batch delivers them: row i = best first, padded with id -1 and

@@ -68,6 +68,7 @@ struct GxDev {           // everything the kernels need, by value
     uint64_t n;
     uint32_t dim, dtype, row_pitch, degree, n_seeds;
     uint32_t S, M, p, T, vwords, max_iters;
+    uint32_t group, ngroups;      // this launch serves the slots s with s % ngroups == group
 };
 
 __device__ __forceinline__ uint32_t gx_key(float f, uint32_t descending)
@@ -188,7 +189,8 @@ template <int DT, int NCH>
 __global__ __launch_bounds__(GX_THREADS) void gx_distance_kernel(GxDev D)
 {
     extern __shared__ __attribute__((aligned(16))) uint8_t gx_q[];
-    const uint32_t s = blockIdx.x, tid = threadIdx.x;
+    const uint32_t s = blockIdx.x * D.ngroups + D.group, tid = threadIdx.x;
+    if (s >= D.S) return;
     const GxMeta m = D.meta[s];
     if (m.state != 1u || m.n_tasks == 0) return;
     const uint32_t pieces = D.row_pitch / 16;
@@ -250,7 +252,8 @@ __global__ __launch_bounds__(GX_THREADS) void gx_merge_extend_kernel(GxDev D, ui
     __shared__ uint32_t parent[TRI_GRAPH_TASK_LIMIT];
     __shared__ uint32_t wave_cnt[4];
     __shared__ uint32_t changed, n_sh;
-    const uint32_t s = blockIdx.x, tid = threadIdx.x;
+    const uint32_t s = blockIdx.x * D.ngroups + D.group, tid = threadIdx.x;
+    if (s >= D.S) return;
     GxMeta *mp = D.meta + s;
     const GxMeta m = *mp;
     if (m.state != 1u) return;                                    // (idle slot: masked)
@@ -368,6 +371,11 @@ struct GStep {
     hipEvent_t done = nullptr, ev0 = nullptr, ev1 = nullptr;
     uint8_t *up_host = nullptr, *up_dev = nullptr;
     uint8_t *down_host = nullptr, *down_dev = nullptr;
+    hipStream_t stream = nullptr;     // the group's stream (group 0: the caller's)
+    bool own_stream = false;
+    uint8_t *upload = nullptr;        // the group's device copy of the upload block
+    std::vector<uint32_t> free_slots;
+    uint32_t n_running = 0;
 };
 
 #define GHIP(expr)                                                                                   \
@@ -384,11 +392,11 @@ struct tri_gpool {
     hipStream_t stream = nullptr;
     std::mutex mu;
     GxDev D{};
-    uint32_t depth = 2, rec_words = 0;
+    uint32_t ngroups = 2, rec_words = 0;
     size_t up_bytes = 0, down_bytes = 0;
     uint8_t *pinned = nullptr, *qstore = nullptr, *qstore_dev = nullptr;
     std::vector<GTicket> tickets;
-    std::vector<uint32_t> free_tickets, free_slots, slot_ticket;
+    std::vector<uint32_t> free_tickets, slot_ticket;
     std::vector<uint32_t> res_ids;
     std::vector<float> res_score;
     std::deque<uint32_t> pending[2];
@@ -401,7 +409,7 @@ struct tri_gpool {
 namespace {
 
 struct GLayout {
-    size_t vecs, vnorm, graph, seeds, slot_q, qnorm, meta, topm, visited, tasks, tdist, upload, total;
+    size_t vecs, vnorm, graph, seeds, slot_q, qnorm, meta, topm, visited, tasks, tdist, upload, upload_one, total;
     uint32_t row_pitch, vwords, T;
 };
 
@@ -413,7 +421,7 @@ int g_validate(const tri_graph_cfg *c, uint64_t n, uint32_t dim, uint32_t degree
     if (degree == 0 || c->parents == 0 || (uint64_t)c->parents * degree > TRI_GRAPH_TASK_LIMIT)
         return tri_fail(TRI_EINVAL, "need parents >= 1, degree >= 1 and parents * degree <= %u", TRI_GRAPH_TASK_LIMIT);
     if (c->max_outstanding < c->slots) return tri_fail(TRI_EINVAL, "max_outstanding must be >= slots");
-    if (c->depth > GRING) return tri_fail(TRI_EINVAL, "depth must be 0..%u", GRING);
+    if (c->groups > GRING) return tri_fail(TRI_EINVAL, "groups must be 0..%u", GRING);
     if (n == 0 || n >= (1ull << 31)) return tri_fail(TRI_EINVAL, "n must be 1..2^31-1");
     if (dtype != TRI_F32 && dtype != TRI_F16) return tri_fail(TRI_EINVAL, "dtype must be TRI_F32 or TRI_F16");
     if (dim == 0 || gup((size_t)dim * (dtype == TRI_F16 ? 2 : 4), 256) > TRI_MAX_ROW_BYTES)
@@ -441,7 +449,8 @@ GLayout g_layout(const tri_graph_cfg &c, uint64_t n, uint32_t dim, uint32_t degr
     L.visited = take(S * L.vwords * 4);
     L.tasks = take(S * L.T * 4);
     L.tdist = take(S * L.T * 4);
-    L.upload = take(sizeof(GxHdr) + S * sizeof(GxNewDesc));
+    L.upload_one = gup(sizeof(GxHdr) + S * sizeof(GxNewDesc), 256);
+    L.upload = take(L.upload_one * GRING);
     L.total = o;
     return L;
 }
@@ -475,7 +484,8 @@ int g_reap(tri_gpool *P, bool block, uint32_t *finished)
             memcpy(&P->res_ids[(size_t)ti * M], rec + 4, (size_t)t.n_out * 4);
             memcpy(&P->res_score[(size_t)ti * M], rec + 4 + M, (size_t)t.n_out * 4);
             t.state = G_DONE;
-            P->free_slots.push_back(slot);
+            R->free_slots.push_back(slot);
+            --R->n_running;
             --P->n_running;
             if (finished) ++*finished;
         }
@@ -493,15 +503,14 @@ int g_reap(tri_gpool *P, bool block, uint32_t *finished)
 }
 
 template <int DT>
-hipError_t g_launch_distance(const tri_gpool *P)
+hipError_t g_launch_distance(const tri_gpool *P, const GxDev &D, uint32_t nblocks, hipStream_t stream)
 {
-    const GxDev &D = P->D;
-    const dim3 grid(D.S), block(GX_THREADS);
+    const dim3 grid(nblocks), block(GX_THREADS);
     const size_t lds = D.row_pitch;
     switch (D.row_pitch / 256) {
-    case 2: hipLaunchKernelGGL((gx_distance_kernel<DT, 2>), grid, block, lds, P->stream, D); break;
-    case 6: hipLaunchKernelGGL((gx_distance_kernel<DT, 6>), grid, block, lds, P->stream, D); break;
-    default: hipLaunchKernelGGL((gx_distance_kernel<DT, 0>), grid, block, lds, P->stream, D); break;
+    case 2: hipLaunchKernelGGL((gx_distance_kernel<DT, 2>), grid, block, lds, stream, D); break;
+    case 6: hipLaunchKernelGGL((gx_distance_kernel<DT, 6>), grid, block, lds, stream, D); break;
+    default: hipLaunchKernelGGL((gx_distance_kernel<DT, 0>), grid, block, lds, stream, D); break;
     }
     return hipGetLastError();
 }
@@ -551,7 +560,7 @@ extern "C" int graph_pool_create(const tri_graph_cfg *cfg, const void *vectors, 
     tri_gpool *P = new (std::nothrow) tri_gpool();
     if (!P) return tri_fail(TRI_ENOMEM, "out of host memory");
     P->cfg = *cfg;
-    P->depth = cfg->depth ? cfg->depth : 2u;
+    P->ngroups = std::min<uint32_t>(cfg->groups ? cfg->groups : 2u, cfg->slots);
     P->stream = (hipStream_t)cfg->hip_stream;
     hipError_t e = hipGetDevice(&P->device);
     if (e != hipSuccess) { delete P; return tri_fail(TRI_EHIP, "hipGetDevice -> %s", hipGetErrorString(e)); }
@@ -562,6 +571,7 @@ extern "C" int graph_pool_create(const tri_graph_cfg *cfg, const void *vectors, 
     D.meta = (GxMeta *)(base + L.meta); D.topm = (unsigned long long *)(base + L.topm);
     D.visited = (uint32_t *)(base + L.visited); D.tasks = (uint32_t *)(base + L.tasks); D.tdist = (float *)(base + L.tdist);
     D.upload = base + L.upload;
+    D.group = 0; D.ngroups = P->ngroups;
     D.n = n; D.dim = dim; D.dtype = dtype; D.row_pitch = L.row_pitch; D.degree = degree; D.n_seeds = n_seeds;
     D.S = cfg->slots; D.M = cfg->topm; D.p = cfg->parents; D.T = L.T; D.vwords = L.vwords; D.max_iters = cfg->max_iters;
     // index data: rows padded with zeros, neighbour list, entry points, row norms, idle slots
@@ -596,12 +606,18 @@ extern "C" int graph_pool_create(const tri_graph_cfg *cfg, const void *vectors, 
         if (e == hipSuccess) e = hipEventCreateWithFlags(&R.done, hipEventDisableTiming);
         if (e == hipSuccess) e = hipEventCreateWithFlags(&R.ev0, hipEventDisableSystemFence);
         if (e == hipSuccess) e = hipEventCreateWithFlags(&R.ev1, hipEventDisableSystemFence);
+        R.upload = base + L.upload + i * L.upload_one;
+        R.stream = P->stream;
+        if (i > 0 && i < P->ngroups && e == hipSuccess) {        // (default priority, like the caller's stream)
+            e = hipStreamCreateWithFlags(&R.stream, hipStreamNonBlocking);
+            R.own_stream = e == hipSuccess;
+        }
     }
     if (e != hipSuccess) { graph_pool_destroy(P); return tri_fail(TRI_EHIP, "pinned memory / events -> %s", hipGetErrorString(e)); }
     try {
         P->tickets.resize(cfg->max_outstanding);
         for (uint32_t i = cfg->max_outstanding; i-- > 0;) P->free_tickets.push_back(i);
-        for (uint32_t i = cfg->slots; i-- > 0;) P->free_slots.push_back(i);
+        for (uint32_t i = cfg->slots; i-- > 0;) P->ring[i % P->ngroups].free_slots.push_back(i);
         P->slot_ticket.assign(cfg->slots, 0);
         P->res_ids.resize((size_t)cfg->max_outstanding * cfg->topm);
         P->res_score.resize((size_t)cfg->max_outstanding * cfg->topm);
@@ -619,6 +635,7 @@ extern "C" int graph_pool_destroy(tri_gpool *P)
     if (!P) return tri_fail(TRI_EINVAL, "pool is NULL");
     (void)hipStreamSynchronize(P->stream);
     for (uint32_t i = 0; i < GRING; ++i) {
+        if (P->ring[i].own_stream) { (void)hipStreamSynchronize(P->ring[i].stream); (void)hipStreamDestroy(P->ring[i].stream); }
         if (P->ring[i].done) (void)hipEventDestroy(P->ring[i].done);
         if (P->ring[i].ev0) (void)hipEventDestroy(P->ring[i].ev0);
         if (P->ring[i].ev1) (void)hipEventDestroy(P->ring[i].ev1);
@@ -671,40 +688,32 @@ extern "C" int graph_step(tri_gpool *P, tri_graph_step_stats *st)
     tri_graph_step_stats stats{};
     int rc = g_reap(P, false, &stats.finished);
     if (rc) return rc;
-    // at most `depth` steps in flight: wait for the oldest
-    for (;;) {
-        uint32_t in_flight = 0;
-        GStep *oldest = nullptr;
-        for (uint32_t i = 0; i < GRING; ++i)
-            if (P->ring[i].in_use) {
-                ++in_flight;
-                if (!oldest || P->ring[i].seq < oldest->seq) oldest = &P->ring[i];
-            }
-        if (in_flight < P->depth) break;
-        GHIP(hipEventSynchronize(oldest->done));
+    // this call serves one group of slots; its previous step must have completed (its slots are then known)
+    const uint32_t g = (uint32_t)(P->step_seq % P->ngroups);
+    GStep &R = P->ring[g];
+    if (R.in_use) {
+        GHIP(hipEventSynchronize(R.done));
         rc = g_reap(P, false, &stats.finished);
         if (rc) return rc;
+        if (R.in_use) return tri_fail(TRI_EHIP, "internal: a completed step was not collected");
     }
-    GStep *Rp = nullptr;
-    for (uint32_t i = 0; i < GRING; ++i)
-        if (!P->ring[i].in_use) { Rp = &P->ring[i]; break; }
-    GStep &R = *Rp;
     // admit: high class first, first-in first-out inside a class
     GxHdr *hdr = (GxHdr *)R.up_host;
     GxNewDesc *desc = (GxNewDesc *)(R.up_host + sizeof(GxHdr));
     uint32_t n_new = 0;
     for (int klass = 0; klass < 2; ++klass) {
         std::deque<uint32_t> &Q = P->pending[klass];
-        while (!Q.empty() && !P->free_slots.empty()) {
+        while (!Q.empty() && !R.free_slots.empty()) {
             const uint32_t ti = Q.front();
             Q.pop_front();
-            const uint32_t slot = P->free_slots.back();
-            P->free_slots.pop_back();
+            const uint32_t slot = R.free_slots.back();
+            R.free_slots.pop_back();
             GTicket &t = P->tickets[ti];
             t.state = G_RUNNING;
             t.slot = slot;
             P->slot_ticket[slot] = ti;
             desc[n_new++] = GxNewDesc{slot, t.k, t.metric, 0u, (uint64_t)(uintptr_t)t.dev_vec, 0ull};
+            ++R.n_running;
             ++P->n_running;
         }
     }
@@ -712,29 +721,33 @@ extern "C" int graph_step(tri_gpool *P, tri_graph_step_stats *st)
     stats.admitted = n_new;
     stats.running = P->n_running;
     stats.pending = (uint32_t)(P->pending[0].size() + P->pending[1].size());
-    if (P->n_running == 0) {
+    ++P->step_seq;                                  // (the next call serves the next group)
+    if (R.n_running == 0) {
         if (st) *st = stats;
         return TRI_OK;
     }
     hdr->n16 = (uint32_t)((sizeof(GxHdr) + (size_t)n_new * sizeof(GxNewDesc) + 15) / 16);
     hdr->n_new = n_new;
     memset(R.down_host, 0, (size_t)P->cfg.slots * 4);   // (this entry's previous step has been collected: the block is ours)
-    hipStream_t s = P->stream;
-    const GxDev &D = P->D;
+    hipStream_t s = R.stream;
+    GxDev D = P->D;
+    D.upload = R.upload;
+    D.group = g;
+    const uint32_t nblocks = (D.S - g + D.ngroups - 1) / D.ngroups;      // slots of this group
     const bool prof = (P->cfg.flags & TRI_FLAG_PROFILE) != 0;
     hipLaunchKernelGGL(gx_pull_kernel, dim3((hdr->n16 + 255) / 256), dim3(256), 0, s, (uint4 *)D.upload, (const uint4 *)R.up_dev);
     if (n_new) hipLaunchKernelGGL(gx_admit_kernel, dim3(n_new), dim3(GX_THREADS), 0, s, D);
     GHIP(hipGetLastError());
     if (prof) GHIP(hipEventRecord(R.ev0, s));
-    GHIP(D.dtype == TRI_F16 ? g_launch_distance<TRI_F16>(P) : g_launch_distance<TRI_F32>(P));
+    GHIP(D.dtype == TRI_F16 ? g_launch_distance<TRI_F16>(P, D, nblocks, s) : g_launch_distance<TRI_F32>(P, D, nblocks, s));
     if (prof) GHIP(hipEventRecord(R.ev1, s));
-    hipLaunchKernelGGL(gx_merge_extend_kernel, dim3(D.S), dim3(GX_THREADS), 0, s, D, (uint32_t *)R.down_dev,
+    hipLaunchKernelGGL(gx_merge_extend_kernel, dim3(nblocks), dim3(GX_THREADS), 0, s, D, (uint32_t *)R.down_dev,
                        (uint32_t *)R.down_dev + D.S, P->rec_words);
     GHIP(hipGetLastError());
     GHIP(hipEventRecord(R.done, s));
     R.in_use = true;
     R.profiled = prof;
-    R.seq = P->step_seq++;
+    R.seq = stats.step;
     if (st) *st = stats;
     return TRI_OK;
 }

@@ -20,7 +20,7 @@ TRI_GRAPH_PAD = 0xFFFFFFFF
 
 class tri_graph_cfg(ctypes.Structure):
     _fields_ = [("slots", ctypes.c_uint32), ("topm", ctypes.c_uint32), ("parents", ctypes.c_uint32),
-                ("max_iters", ctypes.c_uint32), ("max_outstanding", ctypes.c_uint32), ("depth", ctypes.c_uint32),
+                ("max_iters", ctypes.c_uint32), ("max_outstanding", ctypes.c_uint32), ("groups", ctypes.c_uint32),
                 ("flags", ctypes.c_uint32), ("pad_", ctypes.c_uint32), ("hip_stream", ctypes.c_void_p)]
 
 
@@ -63,7 +63,7 @@ class GraphPool:
     """One graph index resident on the GPU and the slot table that serves it."""
 
     def __init__(self, vectors, neighbors, seeds: np.ndarray, dtype: int, slots: int, topm: int, parents: int,
-                 max_iters: int, max_outstanding: int = 0, depth: int = 0, flags: int = 0, own_stream: bool = False):
+                 max_iters: int, max_outstanding: int = 0, groups: int = 0, flags: int = 0, own_stream: bool = False):
         import torch
         if not torch.cuda.is_available():
             raise RuntimeError("no GPU: the search path has no CPU fallback")
@@ -71,7 +71,7 @@ class GraphPool:
         degree = int(neighbors.shape[1])
         assert int(neighbors.shape[0]) == n
         self._stream = torch.cuda.Stream() if own_stream else torch.cuda.current_stream()
-        self.cfg = tri_graph_cfg(slots, topm, parents, max_iters, max_outstanding or 4 * slots, depth, flags, 0,
+        self.cfg = tri_graph_cfg(slots, topm, parents, max_iters, max_outstanding or 4 * slots, groups, flags, 0,
                                  self._stream.cuda_stream)
         nbytes = ctypes.c_size_t(0)
         _check(_lib.graph_pool_bytes(ctypes.byref(self.cfg), n, dim, degree, dtype, ctypes.byref(nbytes)), "graph_pool_bytes")

@@ -81,11 +81,11 @@ def test_integer_data_trajectories_equal_the_oracle(np_dtype, dim):
     metric = (np.arange(nq) % 2).astype(np.uint32)
     dt = tri.TRI_F16 if np_dtype == np.float16 else tri.TRI_F32
     want = _oracle_all(X, G, seeds, Q, k, metric, M, p, iters)
-    for slots, depth in ((64, 2), (300, 1), (7, 4)):
+    for slots, groups in ((64, 2), (300, 1), (7, 4), (2, 3)):
         with tg.GraphPool(X, G, seeds, dt, slots=slots, topm=M, parents=p, max_iters=iters, max_outstanding=1024,
-                          depth=depth) as pool:
+                          groups=groups) as pool:
             ids, dist, n_out, it, ev, steps = pool.run_all(Q, k, metric)
-            _say(f"{np_dtype.__name__} dim {dim}: {slots} slots, depth {depth}: {steps} steps, "
+            _say(f"{np_dtype.__name__} dim {dim}: {slots} slots in {groups} groups: {steps} steps, "
                  f"mean extends {it.mean():.1f}, mean evaluations {ev.mean():.0f}")
             _check_exact((ids, dist, n_out, it, ev), want, k)
             # the same pool again, queries from device memory, the other class mix: identical

@@ -199,7 +199,7 @@ int main(void) {
     assert size.value >= 100000 * (1536 + 4 + 32 * 4) + 64 * (100000 // 8)
     for bad in (tg.tri_graph_cfg(0, 64, 4, 32, 256, 0, 0, 0, None), tg.tri_graph_cfg(64, 257, 4, 32, 256, 0, 0, 0, None),
                 tg.tri_graph_cfg(64, 64, 9, 32, 256, 0, 0, 0, None), tg.tri_graph_cfg(64, 64, 4, 32, 32, 0, 0, 0, None),
-                tg.tri_graph_cfg(64, 64, 4, 32, 256, 5, 0, 0, None)):
+                tg.tri_graph_cfg(64, 64, 4, 32, 256, 5, 0, 0, None)):   # groups > 4
         assert lib.graph_pool_bytes(ctypes.byref(bad), 100000, 768, 32, tri.TRI_F16, ctypes.byref(size)) == tri.TRI_EINVAL
     assert lib.graph_pool_bytes(ctypes.byref(ok), 0, 768, 32, tri.TRI_F16, ctypes.byref(size)) == tri.TRI_EINVAL
     assert lib.graph_pool_bytes(ctypes.byref(ok), 1000, 5000, 32, tri.TRI_F16, ctypes.byref(size)) == tri.TRI_EINVAL
