@@ -52,7 +52,7 @@ typedef struct {
                                   merge of one group runs beside the bandwidth-bound distance launch of
                                   another, and a step is enqueued knowing which of its group's slots the
                                   previous one freed: 1..4 (0 = 2)                                      */
-    uint32_t flags;            /* TRI_FLAG_PROFILE: bracket the distance kernel with HIP events          */
+    uint32_t flags;            /* TRI_FLAG_PROFILE: bracket the step kernel with HIP events              */
     uint32_t pad_;
     void *hip_stream;          /* stream all work is enqueued on (hipStream_t); NULL = default stream    */
 } tri_graph_cfg;
@@ -108,13 +108,14 @@ int graph_poll(tri_gpool *pool, const tri_ticket *t /*[host] n*/, uint32_t n, ui
 /* Block until every enqueued step has completed and collect their results. */
 int graph_sync(tri_gpool *pool);
 
-/* Accumulated since the last reset (TRI_FLAG_PROFILE): launches of the distance kernel, their summed
- * duration (HIP events on the pool's stream) and the distance tasks they scored; a task reads one
- * padded row (row_bytes) -- the kernel's algorithmic bytes. */
+/* Accumulated since the last reset (TRI_FLAG_PROFILE): launches of the step kernel (distances, merge
+ * and next extend of every slot of a group), their summed duration (HIP events on the group's stream)
+ * and the distance tasks they scored; a task reads one padded row (row_bytes) -- the kernel's
+ * algorithmic bytes. */
 typedef struct {
     uint64_t steps;
     uint64_t tasks;
-    double distance_ms;
+    double step_kernel_ms;
     uint32_t row_bytes;
     uint32_t pad_;
 } tri_graph_times;

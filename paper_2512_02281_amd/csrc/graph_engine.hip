@@ -1,15 +1,16 @@
 // The paper's own engine (Sec. 3.2): continuous batching of best-first searches over a fixed-degree
 // neighbour graph, one "extend" of every running request per step.  Per request and on the device: a
 // candidate list topM (sorted composites of score key, id and an "expanded" mark), a visited bit table
-// (one bit per database row, so "first seen" is exact), its query row.  A step is two fixed-shape
-// launches over all S slots -- idle slots leave at once, which is the masked padding of the paper's
-// fixed-shape task array:
-//   distance       : every task of every slot = one gathered row against the slot's query, 16 lanes per task;
-//   merge + extend : tasks' (score, id) + topM -> new topM; stop rule; finished requests write their
-//                    record into the step's pinned result block; the others select up to p non-expanded
-//                    parents of the new topM, read their D neighbours, filter by visited and leave the
-//                    survivors (at most p * D) as the slot's distance tasks of the next step.
-// A newly admitted request enters with its entry points as tasks (admit kernel, before the distance launch).
+// (one bit per database row, so "first seen" is exact), its query row.  A step is ONE fixed-shape launch
+// over the slots of a group, a workgroup per slot -- idle slots leave at once, which is the masked padding
+// of the paper's fixed-shape task array -- in three phases:
+//   distance : every task of the slot = one gathered row against the slot's query, 16 lanes per task;
+//   merge    : tasks' (score, id) + topM -> new topM; stop rule; a finished request writes its record
+//              into the step's pinned result block;
+//   extend   : a request that goes on selects up to p non-expanded parents of the new topM, reads their
+//              D neighbours, filters by visited and leaves the survivors (at most p * D) as its distance
+//              tasks of the next step.
+// A newly admitted request enters with its entry points as tasks (admit kernel, before the step launch).
 #include "../../include/trinity_graph.h"
 #include "tri_common.h"
 
@@ -63,7 +64,6 @@ struct GxDev {           // everything the kernels need, by value
     unsigned long long *topm;
     uint32_t *visited;
     uint32_t *tasks;
-    float *tdist;
     uint8_t *upload;
     uint64_t n;
     uint32_t dim, dtype, row_pitch, degree, n_seeds;
@@ -185,14 +185,12 @@ __device__ __forceinline__ float gx_dot16(const uint4 &x, const uint4 &q, float 
     return acc;
 }
 
+extern __shared__ __attribute__((aligned(16))) uint8_t gx_q[];   // the slot's query row
+
 template <int DT, int NCH>
-__global__ __launch_bounds__(GX_THREADS) void gx_distance_kernel(GxDev D)
+__device__ __forceinline__ void gx_distance_phase(const GxDev &D, uint32_t s, const GxMeta &m, float *__restrict__ sdist)
 {
-    extern __shared__ __attribute__((aligned(16))) uint8_t gx_q[];
-    const uint32_t s = blockIdx.x * D.ngroups + D.group, tid = threadIdx.x;
-    if (s >= D.S) return;
-    const GxMeta m = D.meta[s];
-    if (m.state != 1u || m.n_tasks == 0) return;
+    const uint32_t tid = threadIdx.x;
     const uint32_t pieces = D.row_pitch / 16;
     for (uint32_t i = tid; i < pieces; i += GX_THREADS)
         ((uint4 *)gx_q)[i] = ((const uint4 *)(D.slot_q + (size_t)s * D.row_pitch))[i];
@@ -215,7 +213,7 @@ __global__ __launch_bounds__(GX_THREADS) void gx_distance_kernel(GxDev D)
         }
 #pragma unroll
         for (int d = GX_TEAM / 2; d > 0; d >>= 1) acc += __shfl_xor(acc, d, GX_TEAM);
-        if (c == 0) D.tdist[(size_t)s * D.T + t] = m.metric == TRI_L2 ? (D.vnorm[id] + qn) - 2.0f * acc : acc;
+        if (c == 0) sdist[t] = m.metric == TRI_L2 ? (D.vnorm[id] + qn) - 2.0f * acc : acc;
     }
 }
 
@@ -242,8 +240,10 @@ __device__ __forceinline__ uint32_t gx_count_below(const unsigned long long *a, 
     return lo;
 }
 
-__global__ __launch_bounds__(GX_THREADS) void gx_merge_extend_kernel(GxDev D, uint32_t *__restrict__ done,
-                                                                     uint32_t *__restrict__ rec_base, uint32_t rec_words)
+__device__ __forceinline__ void gx_merge_extend_phase(const GxDev &D, uint32_t s, GxMeta *mp, const GxMeta &m,
+                                                      const float *__restrict__ sdist, unsigned long long old_e,
+                                                      uint32_t task_id, uint32_t *__restrict__ done,
+                                                      uint32_t *__restrict__ rec_base, uint32_t rec_words)
 {
     __shared__ unsigned long long old[TRI_GRAPH_TOPM_LIMIT];
     __shared__ unsigned long long nw[TRI_GRAPH_TASK_LIMIT];
@@ -252,20 +252,15 @@ __global__ __launch_bounds__(GX_THREADS) void gx_merge_extend_kernel(GxDev D, ui
     __shared__ uint32_t parent[TRI_GRAPH_TASK_LIMIT];
     __shared__ uint32_t wave_cnt[4];
     __shared__ uint32_t changed, n_sh;
-    const uint32_t s = blockIdx.x * D.ngroups + D.group, tid = threadIdx.x;
-    if (s >= D.S) return;
-    GxMeta *mp = D.meta + s;
-    const GxMeta m = *mp;
-    if (m.state != 1u) return;                                    // (idle slot: masked)
+    const uint32_t tid = threadIdx.x;
     const uint32_t desc = m.metric == TRI_IP;
     const uint32_t nt = m.n_tasks, M = D.M;
     if (tid == 0) { changed = 0; n_sh = 0; }
     unsigned long long mine = ~0ull;                              // this thread's new pair (T <= 256 = threads)
     if (tid < nt)
-        mine = ((unsigned long long)gx_key(D.tdist[(size_t)s * D.T + tid], desc) << 32) |
-               ((unsigned long long)D.tasks[(size_t)s * D.T + tid] << 1);
+        mine = ((unsigned long long)gx_key(sdist[tid], desc) << 32) | ((unsigned long long)task_id << 1);
     nw[tid] = mine;
-    if (tid < M) { old[tid] = D.topm[(size_t)s * M + tid]; out[tid] = ~0ull; }
+    if (tid < M) { old[tid] = old_e; out[tid] = ~0ull; }
     __syncthreads();
     uint32_t r_new = 0;
     if (tid < nt)
@@ -347,6 +342,29 @@ __global__ __launch_bounds__(GX_THREADS) void gx_merge_extend_kernel(GxDev D, ui
     }
 }
 
+// ------------------------------------------------------------------------------------------ the step
+// One workgroup per slot runs the slot's whole step: distances of its tasks, merge, stop rule, next
+// extend.  Slots are independent of each other, so while one workgroup is in its latency-bound merge and
+// extend the others on the same compute unit keep the memory system busy with their row reads: the step
+// costs about what its row traffic costs, not the sum of its phases.
+template <int DT, int NCH>
+__global__ __launch_bounds__(GX_THREADS) void gx_step_kernel(GxDev D, uint32_t *__restrict__ done,
+                                                             uint32_t *__restrict__ rec_base, uint32_t rec_words)
+{
+    __shared__ float sdist[TRI_GRAPH_TASK_LIMIT];
+    const uint32_t s = blockIdx.x * D.ngroups + D.group;
+    if (s >= D.S) return;
+    GxMeta *mp = D.meta + s;
+    const GxMeta m = *mp;
+    if (m.state != 1u) return;                                    // (idle slot: masked)
+    // what the merge needs from memory is asked for now and arrives while the rows are being read
+    const unsigned long long old_e = threadIdx.x < D.M ? D.topm[(size_t)s * D.M + threadIdx.x] : ~0ull;
+    const uint32_t task_id = threadIdx.x < m.n_tasks ? D.tasks[(size_t)s * D.T + threadIdx.x] : TRI_GRAPH_PAD;
+    if (m.n_tasks) gx_distance_phase<DT, NCH>(D, s, m, sdist);
+    __syncthreads();
+    gx_merge_extend_phase(D, s, mp, m, sdist, old_e, task_id, done, rec_base, rec_words);
+}
+
 // ================================================================================== host side
 inline int64_t gnow_ns()
 {
@@ -409,7 +427,7 @@ struct tri_gpool {
 namespace {
 
 struct GLayout {
-    size_t vecs, vnorm, graph, seeds, slot_q, qnorm, meta, topm, visited, tasks, tdist, upload, upload_one, total;
+    size_t vecs, vnorm, graph, seeds, slot_q, qnorm, meta, topm, visited, tasks, upload, upload_one, total;
     uint32_t row_pitch, vwords, T;
 };
 
@@ -448,7 +466,6 @@ GLayout g_layout(const tri_graph_cfg &c, uint64_t n, uint32_t dim, uint32_t degr
     L.topm = take(S * c.topm * 8);
     L.visited = take(S * L.vwords * 4);
     L.tasks = take(S * L.T * 4);
-    L.tdist = take(S * L.T * 4);
     L.upload_one = gup(sizeof(GxHdr) + S * sizeof(GxNewDesc), 256);
     L.upload = take(L.upload_one * GRING);
     L.total = o;
@@ -493,7 +510,7 @@ int g_reap(tri_gpool *P, bool block, uint32_t *finished)
             float ms = 0.f;
             GHIP(hipEventElapsedTime(&ms, R->ev0, R->ev1));
             P->times.steps += 1;
-            P->times.distance_ms += ms;
+            P->times.step_kernel_ms += ms;
             P->times.tasks += tasks;        // (tasks of the requests that finished in the step: over a run from idle
                                             //  to idle this adds up to every task scored)
         }
@@ -503,14 +520,15 @@ int g_reap(tri_gpool *P, bool block, uint32_t *finished)
 }
 
 template <int DT>
-hipError_t g_launch_distance(const tri_gpool *P, const GxDev &D, uint32_t nblocks, hipStream_t stream)
+hipError_t g_launch_step(const GxDev &D, uint32_t nblocks, hipStream_t stream, uint32_t *done, uint32_t *rec_base,
+                         uint32_t rec_words)
 {
     const dim3 grid(nblocks), block(GX_THREADS);
     const size_t lds = D.row_pitch;
     switch (D.row_pitch / 256) {
-    case 2: hipLaunchKernelGGL((gx_distance_kernel<DT, 2>), grid, block, lds, stream, D); break;
-    case 6: hipLaunchKernelGGL((gx_distance_kernel<DT, 6>), grid, block, lds, stream, D); break;
-    default: hipLaunchKernelGGL((gx_distance_kernel<DT, 0>), grid, block, lds, stream, D); break;
+    case 2: hipLaunchKernelGGL((gx_step_kernel<DT, 2>), grid, block, lds, stream, D, done, rec_base, rec_words); break;
+    case 6: hipLaunchKernelGGL((gx_step_kernel<DT, 6>), grid, block, lds, stream, D, done, rec_base, rec_words); break;
+    default: hipLaunchKernelGGL((gx_step_kernel<DT, 0>), grid, block, lds, stream, D, done, rec_base, rec_words); break;
     }
     return hipGetLastError();
 }
@@ -569,7 +587,7 @@ extern "C" int graph_pool_create(const tri_graph_cfg *cfg, const void *vectors, 
     D.vecs = base + L.vecs; D.vnorm = (float *)(base + L.vnorm); D.graph = (uint32_t *)(base + L.graph);
     D.seeds = (uint32_t *)(base + L.seeds); D.slot_q = base + L.slot_q; D.qnorm = (float *)(base + L.qnorm);
     D.meta = (GxMeta *)(base + L.meta); D.topm = (unsigned long long *)(base + L.topm);
-    D.visited = (uint32_t *)(base + L.visited); D.tasks = (uint32_t *)(base + L.tasks); D.tdist = (float *)(base + L.tdist);
+    D.visited = (uint32_t *)(base + L.visited); D.tasks = (uint32_t *)(base + L.tasks);
     D.upload = base + L.upload;
     D.group = 0; D.ngroups = P->ngroups;
     D.n = n; D.dim = dim; D.dtype = dtype; D.row_pitch = L.row_pitch; D.degree = degree; D.n_seeds = n_seeds;
@@ -739,11 +757,10 @@ extern "C" int graph_step(tri_gpool *P, tri_graph_step_stats *st)
     if (n_new) hipLaunchKernelGGL(gx_admit_kernel, dim3(n_new), dim3(GX_THREADS), 0, s, D);
     GHIP(hipGetLastError());
     if (prof) GHIP(hipEventRecord(R.ev0, s));
-    GHIP(D.dtype == TRI_F16 ? g_launch_distance<TRI_F16>(P, D, nblocks, s) : g_launch_distance<TRI_F32>(P, D, nblocks, s));
+    uint32_t *done_d = (uint32_t *)R.down_dev;
+    GHIP(D.dtype == TRI_F16 ? g_launch_step<TRI_F16>(D, nblocks, s, done_d, done_d + D.S, P->rec_words)
+                            : g_launch_step<TRI_F32>(D, nblocks, s, done_d, done_d + D.S, P->rec_words));
     if (prof) GHIP(hipEventRecord(R.ev1, s));
-    hipLaunchKernelGGL(gx_merge_extend_kernel, dim3(nblocks), dim3(GX_THREADS), 0, s, D, (uint32_t *)R.down_dev,
-                       (uint32_t *)R.down_dev + D.S, P->rec_words);
-    GHIP(hipGetLastError());
     GHIP(hipEventRecord(R.done, s));
     R.in_use = true;
     R.profiled = prof;

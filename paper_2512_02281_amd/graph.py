@@ -30,7 +30,7 @@ class tri_graph_step_stats(ctypes.Structure):
 
 
 class tri_graph_times(ctypes.Structure):
-    _fields_ = [("steps", ctypes.c_uint64), ("tasks", ctypes.c_uint64), ("distance_ms", ctypes.c_double),
+    _fields_ = [("steps", ctypes.c_uint64), ("tasks", ctypes.c_uint64), ("step_kernel_ms", ctypes.c_double),
                 ("row_bytes", ctypes.c_uint32), ("pad_", ctypes.c_uint32)]
 
 
