@@ -669,6 +669,7 @@ extern "C" int graph_submit(tri_gpool *P, const void *vecs, int on_device, uint6
 {
     if (n_done) *n_done = 0;
     if (!P || (n && (!vecs || !k || !metric || !out))) return tri_fail(TRI_EINVAL, "NULL argument");
+    if (n == 0) return TRI_OK;
     const size_t es = P->D.dtype == TRI_F16 ? 2 : 4;
     if (pitch_bytes < (uint64_t)P->D.dim * es || pitch_bytes % es) return tri_fail(TRI_EINVAL, "pitch_bytes too small or not a multiple of the element size");
     for (uint32_t i = 0; i < n; ++i) {

@@ -123,6 +123,81 @@ def test_real_valued_data_valid_results_and_recall():
     assert abs(r_gpu - r_orc) <= 0.02 and same >= 0.9 * nq
 
 
+def test_largest_shapes_and_degenerate_graphs():
+    """The limits of the implementation in one pool -- topM 256, parents * degree 256, 256 entry points, rows of
+    4096 bytes, k = topM, a database whose size is no multiple of 32 -- and degenerate graphs: degree 1 (a ring),
+    every neighbour entry padding, a single row."""
+    tri, tg = _lib()
+    rng = np.random.default_rng(3)
+    n, dim = 1003, 2048
+    X = rng.integers(-3, 4, size=(n, dim)).astype(np.float16)
+    Q = rng.integers(-3, 4, size=(40, dim)).astype(np.float16)
+    G = rng.integers(0, n, size=(n, 32)).astype(np.uint32)
+    seeds = rng.choice(n, size=256, replace=False).astype(np.uint32)
+    want = _oracle_all(X, G, seeds, Q, 256, np.arange(40) % 2, 256, 8, 30)
+    with tg.GraphPool(X, G, seeds, tri.TRI_F16, slots=16, topm=256, parents=8, max_iters=30, groups=2) as pool:
+        ids, dist, n_out, it, ev, steps = pool.run_all(Q, 256, (np.arange(40) % 2).astype(np.uint32))
+        _check_exact((ids, dist, n_out, it, ev), want, 256)
+        assert int(ev.max()) > 700                                   # most of the database was scored
+    # a ring of degree 1, one entry point: one new row per extend until the walk stops improving
+    Xr = np.arange(64, dtype=np.float32).reshape(64, 1)
+    Gr = ((np.arange(64) + 1) % 64).astype(np.uint32).reshape(64, 1)
+    qr = np.array([[20.25]], dtype=np.float32)
+    want = _oracle_all(Xr, Gr, [3], qr, 4, tri.TRI_L2, 4, 1, 100)
+    with tg.GraphPool(Xr, Gr, np.array([3], dtype=np.uint32), tri.TRI_F32, slots=1, topm=4, parents=1, max_iters=100) as pool:
+        got = pool.run_all(qr, 4, tri.TRI_L2)
+        _check_exact(got[:5], want, 4)
+        assert int(got[3][0]) == want[0]["iters"] >= 18
+    # no edges at all: the answer is the entry points, after one extend that finds nothing
+    Gp = np.full((64, 2), tg.TRI_GRAPH_PAD, dtype=np.uint32)
+    want = _oracle_all(Xr, Gp, [5, 30, 31], qr, 3, tri.TRI_L2, 8, 2, 10)
+    with tg.GraphPool(Xr, Gp, np.array([5, 30, 31], dtype=np.uint32), tri.TRI_F32, slots=3, topm=8, parents=2, max_iters=10) as pool:
+        got = pool.run_all(qr, 3, tri.TRI_L2)
+        _check_exact(got[:5], want, 3)
+        assert list(got[0][0]) == [30, 31, 5] and int(got[3][0]) == 1
+    # a database of one row
+    X1 = np.array([[2.0, 1.0]], dtype=np.float32)
+    G1 = np.zeros((1, 1), dtype=np.uint32)
+    with tg.GraphPool(X1, G1, np.array([0], dtype=np.uint32), tri.TRI_F32, slots=2, topm=2, parents=1, max_iters=5) as pool:
+        ids, dist, n_out, it, ev, _ = pool.run_all(np.array([[1.0, 1.0]], dtype=np.float32), 2, tri.TRI_IP)
+        assert list(ids[0]) == [0, -1] and dist[0, 0] == 3.0 and int(n_out[0]) == 1 and int(ev[0]) == 1
+        ids, dist, n_out, it, ev, _ = pool.run_all(np.zeros((0, 2), dtype=np.float32), np.zeros(0, dtype=np.uint32),
+                                                   np.zeros(0, dtype=np.uint32))     # an empty batch
+        assert ids.shape[0] == 0
+
+
+@pytest.mark.timeout(600)
+def test_full_size_in_the_benchmark_configuration():
+    """The workload and launch configuration bench.py --workload graph times (1M x 768 fp16, degree 32, topM 128,
+    4 parents, 8192 slots in 3 groups, device-resident queries): a sample of the batch against the oracle, query
+    by query.  On this real-valued data trajectories may differ where scores nearly tie, so every sampled result
+    must be valid and nearly all must equal the oracle's."""
+    import torch
+    tri, tg = _lib()
+    n, dim, D, M, p, iters, k, S = 1_000_000, 768, 32, 128, 4, 64, 10, 8192
+    X, Z = graph_inputs.make_points(n, dim, 12, np.float16, graph_inputs.SEED_POINTS, device="cuda")
+    Qv, _ = graph_inputs.make_points(2 * S, dim, 12, np.float16, graph_inputs.SEED_QUERIES, device="cuda")
+    G = graph_inputs.make_graph(Z, D, 8, graph_inputs.SEED_EDGES, block=1024).to(torch.int32)
+    seeds = graph_inputs.entry_points(n, 64)
+    torch.cuda.synchronize()
+    _say("full size: inputs ready")
+    with tg.GraphPool(X, G, seeds, tri.TRI_F16, slots=S, topm=M, parents=p, max_iters=iters, max_outstanding=4 * S,
+                      groups=3, own_stream=True) as pool:
+        ids, dist, n_out, it, ev, steps = pool.run_all(Qv, k, tri.TRI_IP)
+    Xh, Gh, Qh = X.cpu().numpy(), G.cpu().numpy().astype(np.uint32), Qv.cpu().numpy()
+    sel = np.arange(0, 2 * S, 64)
+    same = 0
+    for i in sel:
+        w = gs.search(Xh, Gh, seeds, Qh[i], k, M, p, iters, gs.METRIC_IP)
+        assert int(n_out[i]) == w["n"] == k and len(set(ids[i].tolist())) == k
+        true_sc = gs.scores(Xh, ids[i], Qh[i], gs.METRIC_IP)
+        assert np.all(np.abs(dist[i] - true_sc) <= 2e-3 * np.abs(true_sc) + 4e-6)
+        assert np.all(dist[i][:-1] >= dist[i][1:])
+        same += np.array_equal(ids[i], w["ids"]) and int(it[i]) == w["iters"] and int(ev[i]) == w["evals"]
+    _say(f"full size: {steps} steps, {same}/{sel.size} sampled queries with the oracle's ids, extends and evaluations")
+    assert same >= 0.97 * sel.size
+
+
 def test_argument_errors_and_empty_steps():
     tri, tg = _lib()
     X = np.arange(32, dtype=np.float32).reshape(16, 2)
