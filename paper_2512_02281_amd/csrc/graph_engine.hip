@@ -2,7 +2,7 @@
 // neighbour graph, one "extend" of every running request per step.  Per request and on the device: a
 // candidate list topM (sorted composites of score key, id and an "expanded" mark), a visited bit table
 // (one bit per database row, so "first seen" is exact), its query row.  A step is ONE fixed-shape launch
-// over the slots of a group, a wavefront per slot -- idle slots leave at once, which is the masked padding
+// over the slots of a group, a workgroup per slot -- idle slots leave at once, which is the masked padding
 // of the paper's fixed-shape task array -- in three phases:
 //   distance : every task of the slot = one gathered row against the slot's query, 16 lanes per task;
 //   merge    : tasks' (score, id) + topM -> new topM; stop rule; a finished request writes its record
@@ -163,35 +163,12 @@ __global__ __launch_bounds__(GX_THREADS) void gx_admit_kernel(GxDev D)
     }
 }
 
-// ------------------------------------------------------------------------------------------ the step
-// ONE WAVEFRONT runs a slot's whole step -- distances of its tasks, merge into topM, stop rule, next
-// extend -- with nothing but wavefront-level synchronisation, four slots to a workgroup.  All slots of a
-// launch are resident at once (8 wavefronts per SIMD) and every wavefront moves at its own pace, so the
-// latency-bound merge and extend of one slot run under the row reads of the others: the launch costs
-// about what its row traffic costs, not the sum of its phases.
-//
-//  distance : a team of 16 lanes per task reads the task's row in 256-byte pieces (16 bytes per lane,
-//             consecutive lanes consecutive addresses: two full 128-byte lines per piece; all pieces of a
-//             row in flight together when the row length is known at compile time, NCH pieces) against the
-//             query row in LDS and reduces in a fixed order, so a score does not depend on what else is in
-//             the launch.  L2 = |x|^2 + |q|^2 - 2 x.q with the stored |x|^2.
-//  merge    : elements are composites (key << 32 | id << 1 | expanded; ids are unique: a row is scored at
-//             most once per request).  topM is sorted already, so only the new pairs are sorted (rank
-//             counting among themselves); the final rank of a new pair is its rank among the new ones plus
-//             the number of topM entries below it (binary search), that of a topM entry its index plus the
-//             number of new pairs below it.  The first M form the new topM; it changed iff a new pair ranks
-//             among them.
-//  stop     : by the paper's rule (topM unchanged), the extend budget, or no parent left.
-//  extend   : a request that goes on selects its next parents at once: the first p non-expanded entries of
-//             the new topM in its order (ballot prefix counts over chunks of 64 entries) are marked; lane t
-//             takes neighbour t % D of parent t / D through the visited filter; the survivors, compacted,
-//             are the slot's distance tasks of the next step.
-// Per wavefront in LDS: the query row | A: 64-bit x Tcap (new pairs, then the same sorted) | B: 64-bit x Mcap
-// (topM, then the new topM) | C: 32-bit x Tcap (scores, then the parents).  Each lane owns elements
-// lane + 64 j, j < GX_PER.
-#define GX_PER 4            // elements per lane: TRI_GRAPH_TOPM_LIMIT / 64 = TRI_GRAPH_TASK_LIMIT / 64
-static_assert(TRI_GRAPH_TOPM_LIMIT == 64 * GX_PER && TRI_GRAPH_TASK_LIMIT == 64 * GX_PER, "four elements per lane");
-
+// ------------------------------------------------------------------------------------------ distance
+// One workgroup per slot, the slot's query row in LDS; a team of 16 lanes per task reads the task's row
+// in 256-byte pieces (16 bytes per lane, consecutive lanes consecutive addresses: two full 128-byte
+// lines per piece) and reduces its dot product in a fixed order, so a score does not depend on which
+// other tasks share the launch.  L2 = |x|^2 + |q|^2 - 2 x.q with the stored |x|^2.
+// NCH = 256-byte pieces per row when known at compile time (all loads of a row in flight together), 0 = any.
 template <int DT>
 __device__ __forceinline__ float gx_dot16(const uint4 &x, const uint4 &q, float acc)
 {
@@ -208,6 +185,51 @@ __device__ __forceinline__ float gx_dot16(const uint4 &x, const uint4 &q, float 
     return acc;
 }
 
+extern __shared__ __attribute__((aligned(16))) uint8_t gx_q[];   // the slot's query row
+
+template <int DT, int NCH>
+__device__ __forceinline__ void gx_distance_phase(const GxDev &D, uint32_t s, const GxMeta &m, float *__restrict__ sdist)
+{
+    const uint32_t tid = threadIdx.x;
+    const uint32_t pieces = D.row_pitch / 16;
+    for (uint32_t i = tid; i < pieces; i += GX_THREADS)
+        ((uint4 *)gx_q)[i] = ((const uint4 *)(D.slot_q + (size_t)s * D.row_pitch))[i];
+    __syncthreads();
+    const uint32_t team = tid / GX_TEAM, c = tid % GX_TEAM;
+    const float qn = D.qnorm[s];
+    const uint32_t nch = NCH ? (uint32_t)NCH : D.row_pitch / 256;
+    for (uint32_t t = team; t < m.n_tasks; t += GX_THREADS / GX_TEAM) {
+        const uint32_t id = D.tasks[(size_t)s * D.T + t];
+        const uint4 *row = (const uint4 *)(D.vecs + (size_t)id * D.row_pitch);
+        float acc = 0.f;
+        if (NCH) {
+            uint4 x[NCH ? NCH : 1];
+#pragma unroll
+            for (int i = 0; i < NCH; ++i) x[i] = row[c + i * GX_TEAM];
+#pragma unroll
+            for (int i = 0; i < NCH; ++i) acc = gx_dot16<DT>(x[i], ((const uint4 *)gx_q)[c + i * GX_TEAM], acc);
+        } else {
+            for (uint32_t i = 0; i < nch; ++i) acc = gx_dot16<DT>(row[c + i * GX_TEAM], ((const uint4 *)gx_q)[c + i * GX_TEAM], acc);
+        }
+#pragma unroll
+        for (int d = GX_TEAM / 2; d > 0; d >>= 1) acc += __shfl_xor(acc, d, GX_TEAM);
+        if (c == 0) sdist[t] = m.metric == TRI_L2 ? (D.vnorm[id] + qn) - 2.0f * acc : acc;
+    }
+}
+
+// ------------------------------------------------------------------------------------------ merge + extend
+// One workgroup per slot.
+//  merge : the step's (score, id) pairs join topM.  Elements are composites (key << 32 | id << 1 | expanded;
+//          ids are unique: a row is scored at most once per request).  topM is sorted already, so only the
+//          new pairs are sorted (rank counting among themselves); the final rank of a new pair is its rank
+//          among the new ones plus the number of topM entries below it (binary search), that of a topM
+//          entry its index plus the number of new pairs below it.  The first M form the new topM; it
+//          changed iff a new pair ranks among them.
+//  stop  : by the paper's rule (topM unchanged), the extend budget, or no parent left.
+//  extend: a request that goes on selects its next parents at once -- thread i looks at entry i of the new
+//          topM: the first p non-expanded ones (in topM's order) become parents and are marked; thread t
+//          takes neighbour t % D of parent t / D through the visited filter; the survivors, compacted, are
+//          the slot's distance tasks of the next step.
 __device__ __forceinline__ uint32_t gx_count_below(const unsigned long long *a, uint32_t n, unsigned long long x)
 {
     uint32_t lo = 0, hi = n;                 // a ascending: number of entries < x
@@ -218,205 +240,129 @@ __device__ __forceinline__ uint32_t gx_count_below(const unsigned long long *a, 
     return lo;
 }
 
-__device__ __forceinline__ uint32_t gx_lanes_before(unsigned long long m)
+__device__ __forceinline__ void gx_merge_extend_phase(const GxDev &D, uint32_t s, GxMeta *mp, const GxMeta &m,
+                                                      const float *__restrict__ sdist, unsigned long long old_e,
+                                                      uint32_t task_id, uint32_t *__restrict__ done,
+                                                      uint32_t *__restrict__ rec_base, uint32_t rec_words)
 {
-    return __builtin_amdgcn_mbcnt_hi((uint32_t)(m >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)m, 0u));
-}
-
-extern __shared__ __attribute__((aligned(16))) uint8_t gx_lds[];
-
-template <int DT, int NCH>
-__global__ __launch_bounds__(GX_THREADS) void gx_step_kernel(GxDev D, uint32_t *__restrict__ done,
-                                                             uint32_t *__restrict__ rec_base, uint32_t rec_words,
-                                                             uint32_t Tcap, uint32_t Mcap)
-{
-    const uint32_t wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
-    const uint32_t s = (blockIdx.x * (GX_THREADS / 64) + wave) * D.ngroups + D.group;
-    if (s >= D.S) return;
-    GxMeta *mp = D.meta + s;
-    const GxMeta m = *mp;
-    if (m.state != 1u) return;                                    // (idle slot: masked)
-    const uint32_t M = D.M, nt = m.n_tasks, desc = m.metric == TRI_IP;
-    uint8_t *base = gx_lds + (size_t)wave * (D.row_pitch + 12u * Tcap + 8u * Mcap);
-    const uint4 *q = (const uint4 *)base;
-    unsigned long long *A = (unsigned long long *)(base + D.row_pitch);
-    unsigned long long *B = A + Tcap;
-    uint32_t *C = (uint32_t *)(B + Mcap);
-    // what the merge needs from memory is asked for now and arrives while the rows are being read
-    unsigned long long old_e[GX_PER];
-    uint32_t task_id[GX_PER];
-#pragma unroll
-    for (int j = 0; j < GX_PER; ++j) {
-        const uint32_t i = lane + 64u * j;
-        old_e[j] = i < M ? D.topm[(size_t)s * M + i] : ~0ull;
-        task_id[j] = i < nt ? D.tasks[(size_t)s * D.T + i] : TRI_GRAPH_PAD;
+    __shared__ unsigned long long old[TRI_GRAPH_TOPM_LIMIT];
+    __shared__ unsigned long long nw[TRI_GRAPH_TASK_LIMIT];
+    __shared__ unsigned long long snew[TRI_GRAPH_TASK_LIMIT];
+    __shared__ unsigned long long out[TRI_GRAPH_TOPM_LIMIT];
+    __shared__ uint32_t parent[TRI_GRAPH_TASK_LIMIT];
+    __shared__ uint32_t wave_cnt[4];
+    __shared__ uint32_t changed, n_sh;
+    const uint32_t tid = threadIdx.x;
+    const uint32_t desc = m.metric == TRI_IP;
+    const uint32_t nt = m.n_tasks, M = D.M;
+    if (tid == 0) { changed = 0; n_sh = 0; }
+    unsigned long long mine = ~0ull;                              // this thread's new pair (T <= 256 = threads)
+    if (tid < nt)
+        mine = ((unsigned long long)gx_key(sdist[tid], desc) << 32) | ((unsigned long long)task_id << 1);
+    nw[tid] = mine;
+    if (tid < M) { old[tid] = old_e; out[tid] = ~0ull; }
+    __syncthreads();
+    uint32_t r_new = 0;
+    if (tid < nt)
+        for (uint32_t j = 0; j < nt; ++j) r_new += nw[j] < mine;
+    if (tid < nt) snew[r_new] = mine;
+    __syncthreads();
+    if (tid < nt) {
+        const uint32_t r = r_new + gx_count_below(old, M, mine);
+        if (r < M) { out[r] = mine; changed = 1u; }               // (benign race: every writer stores 1)
     }
-    // ---- distance: the task ids go through LDS (A is free until the merge), so a team's reads of a row do not
-    //      wait for a read of its id; each team has the rows of two tasks in flight at a time
-    if (nt) {
-        uint32_t *tid_lds = (uint32_t *)A;
-#pragma unroll
-        for (int j = 0; j < GX_PER; ++j)
-            if (lane + 64u * j < nt) tid_lds[lane + 64u * j] = task_id[j];
-        for (uint32_t i = lane; i < D.row_pitch / 16; i += 64) ((uint4 *)base)[i] = ((const uint4 *)(D.slot_q + (size_t)s * D.row_pitch))[i];
-        __builtin_amdgcn_wave_barrier();
-        const uint32_t teams = 64 / GX_TEAM, team = lane / GX_TEAM, c = lane % GX_TEAM;
-        const float qn = D.qnorm[s];
-        const uint32_t nch = NCH ? (uint32_t)NCH : D.row_pitch / 256;
-        for (uint32_t t0 = team; t0 < nt; t0 += 2 * teams) {
-            const uint32_t t1 = t0 + teams < nt ? t0 + teams : t0;           // (no second task: the first again, not stored)
-            const uint32_t id0 = tid_lds[t0], id1 = tid_lds[t1];
-            const uint4 *row0 = (const uint4 *)(D.vecs + (size_t)id0 * D.row_pitch);
-            const uint4 *row1 = (const uint4 *)(D.vecs + (size_t)id1 * D.row_pitch);
-            float acc0 = 0.f, acc1 = 0.f;
-            if (NCH) {
-                uint4 x0[NCH ? NCH : 1], x1[NCH ? NCH : 1];
-#pragma unroll
-                for (int i = 0; i < NCH; ++i) x0[i] = row0[c + i * GX_TEAM];
-#pragma unroll
-                for (int i = 0; i < NCH; ++i) x1[i] = row1[c + i * GX_TEAM];
-#pragma unroll
-                for (int i = 0; i < NCH; ++i) acc0 = gx_dot16<DT>(x0[i], q[c + i * GX_TEAM], acc0);
-#pragma unroll
-                for (int i = 0; i < NCH; ++i) acc1 = gx_dot16<DT>(x1[i], q[c + i * GX_TEAM], acc1);
-            } else {
-                for (uint32_t i = 0; i < nch; ++i) {
-                    const uint4 a = row0[c + i * GX_TEAM], b = row1[c + i * GX_TEAM], qq = q[c + i * GX_TEAM];
-                    acc0 = gx_dot16<DT>(a, qq, acc0);
-                    acc1 = gx_dot16<DT>(b, qq, acc1);
-                }
-            }
-#pragma unroll
-            for (int d = GX_TEAM / 2; d > 0; d >>= 1) {
-                acc0 += __shfl_xor(acc0, d, GX_TEAM);
-                acc1 += __shfl_xor(acc1, d, GX_TEAM);
-            }
-            if (c == 0) {
-                C[t0] = __float_as_uint(m.metric == TRI_L2 ? (D.vnorm[id0] + qn) - 2.0f * acc0 : acc0);
-                if (t1 != t0) C[t1] = __float_as_uint(m.metric == TRI_L2 ? (D.vnorm[id1] + qn) - 2.0f * acc1 : acc1);
-            }
+    if (tid < M) {
+        const unsigned long long e = old[tid];
+        if (e != ~0ull) {                                          // empty entries stay at the end
+            const uint32_t r = tid + gx_count_below(snew, nt, e);
+            if (r < M) out[r] = e;
         }
-        __builtin_amdgcn_wave_barrier();
     }
-    // ---- merge
-    unsigned long long mine[GX_PER];
-    uint32_t r_new[GX_PER];
-#pragma unroll
-    for (int j = 0; j < GX_PER; ++j) {
-        const uint32_t i = lane + 64u * j;
-        mine[j] = i < nt ? ((unsigned long long)gx_key(__uint_as_float(C[i]), desc) << 32) | ((unsigned long long)task_id[j] << 1) : ~0ull;
-        if (i < Tcap) A[i] = mine[j];
-        if (i < M) B[i] = old_e[j];
-        r_new[j] = 0;
-    }
-    __builtin_amdgcn_wave_barrier();
-    for (uint32_t k = 0; k < nt; ++k) {
-        const unsigned long long a = A[k];
-#pragma unroll
-        for (int j = 0; j < GX_PER; ++j) r_new[j] += a < mine[j];
-    }
-    __builtin_amdgcn_wave_barrier();                              // (every lane has read A: it becomes the sorted array)
-#pragma unroll
-    for (int j = 0; j < GX_PER; ++j)
-        if (lane + 64u * j < nt) A[r_new[j]] = mine[j];
-    __builtin_amdgcn_wave_barrier();
-    uint32_t rank_new[GX_PER], rank_old[GX_PER];
-#pragma unroll
-    for (int j = 0; j < GX_PER; ++j) {
-        const uint32_t i = lane + 64u * j;
-        rank_new[j] = i < nt ? r_new[j] + gx_count_below(B, M, mine[j]) : 0xFFFFFFFFu;
-        rank_old[j] = old_e[j] != ~0ull ? i + gx_count_below(A, nt, old_e[j]) : 0xFFFFFFFFu;   // (empty entries stay at the end)
-    }
-    __builtin_amdgcn_wave_barrier();                              // (every lane has read B: it becomes the new topM)
-#pragma unroll
-    for (int j = 0; j < GX_PER; ++j)
-        if (lane + 64u * j < M) B[lane + 64u * j] = ~0ull;
-    __builtin_amdgcn_wave_barrier();
-    bool entered = false;
-#pragma unroll
-    for (int j = 0; j < GX_PER; ++j) {
-        if (rank_new[j] < M) { B[rank_new[j]] = mine[j]; entered = true; }
-        if (rank_old[j] < M) B[rank_old[j]] = old_e[j];
-    }
-    const bool changed = __ballot(entered) != 0ull;
-    __builtin_amdgcn_wave_barrier();
-    // ---- stop rule
+    __syncthreads();
+    // stop rule
     bool finish;
     uint32_t iters = m.iters;
     if (m.fresh) finish = D.max_iters == 0;
     else {
-        iters += 1;                                                // (a running slot is only here with parents)
+        iters += 1;                                                // (a running slot reaches this kernel only with parents)
         finish = !changed || iters >= D.max_iters;
     }
-    // ---- extend
-    unsigned long long top[GX_PER];
-#pragma unroll
-    for (int j = 0; j < GX_PER; ++j) top[j] = lane + 64u * j < M ? B[lane + 64u * j] : ~0ull;
     uint32_t n_par = 0, n_tasks = 0;
     if (!finish) {
-        uint32_t before = 0;                                       // non-expanded entries in the chunks already seen
-#pragma unroll
-        for (int j = 0; j < GX_PER; ++j) {
-            const bool unexp = top[j] != ~0ull && !(top[j] & 1ull);
-            const unsigned long long mk = __ballot(unexp);
-            const uint32_t rank = before + gx_lanes_before(mk);
-            if (unexp && rank < D.p) {
-                C[rank] = (uint32_t)(top[j] & 0xFFFFFFFFull) >> 1;  // (C: the parents now)
-                top[j] |= 1ull;
-            }
-            before += (uint32_t)__popcll(mk);
+        const unsigned long long e = tid < M ? out[tid] : ~0ull;
+        const bool unexp = e != ~0ull && !(e & 1ull);
+        uint32_t total;
+        const uint32_t rank = gx_block_rank(unexp, wave_cnt, &total);
+        if (unexp && rank < D.p) {
+            parent[rank] = (uint32_t)(e & 0xFFFFFFFFull) >> 1;
+            out[tid] = e | 1ull;
         }
-        n_par = before < D.p ? before : D.p;
+        n_par = total < D.p ? total : D.p;
         if (n_par == 0) finish = true;                             // nothing left to expand: not an extend
-        __builtin_amdgcn_wave_barrier();
+        __syncthreads();
     }
     if (!finish) {
-#pragma unroll
-        for (int j = 0; j < GX_PER; ++j) {
-            const uint32_t t = lane + 64u * j;
-            uint32_t v = TRI_GRAPH_PAD;
-            const uint32_t par = t / D.degree, nb = t % D.degree;
-            if (par < n_par) {
-                const uint32_t cnd = D.graph[(size_t)C[par] * D.degree + nb];
-                if (cnd < D.n) {
-                    const uint32_t bit = 1u << (cnd & 31);
-                    const uint32_t was = atomicOr(&D.visited[(size_t)s * D.vwords + (cnd >> 5)], bit);
-                    if (!(was & bit)) v = cnd;
-                }
+        uint32_t v = TRI_GRAPH_PAD;
+        const uint32_t par = tid / D.degree, j = tid % D.degree;
+        if (par < n_par) {
+            const uint32_t c = D.graph[(size_t)parent[par] * D.degree + j];
+            if (c < D.n) {
+                const uint32_t bit = 1u << (c & 31);
+                const uint32_t was = atomicOr(&D.visited[(size_t)s * D.vwords + (c >> 5)], bit);
+                if (!(was & bit)) v = c;
             }
-            const unsigned long long mk = __ballot(v != TRI_GRAPH_PAD);
-            if (v != TRI_GRAPH_PAD) D.tasks[(size_t)s * D.T + n_tasks + gx_lanes_before(mk)] = v;
-            n_tasks += (uint32_t)__popcll(mk);
         }
+        const uint32_t pos = gx_block_rank(v != TRI_GRAPH_PAD, wave_cnt, &n_tasks);
+        if (v != TRI_GRAPH_PAD) D.tasks[(size_t)s * D.T + pos] = v;
     }
-#pragma unroll
-    for (int j = 0; j < GX_PER; ++j)
-        if (lane + 64u * j < M) D.topm[(size_t)s * M + lane + 64u * j] = top[j];
+    if (tid < M) D.topm[(size_t)s * M + tid] = out[tid];
     if (finish) {
-        uint32_t *rec = rec_base + (size_t)s * rec_words;          // [n, iters, evals, 0, ids[M], score bits[M]]
+        uint32_t *rec = rec_base + (size_t)s * rec_words;
         uint32_t n_valid = 0;
-#pragma unroll
-        for (int j = 0; j < GX_PER; ++j) {
-            const uint32_t i = lane + 64u * j;
-            const bool ok = top[j] != ~0ull && i < m.k;
-            if (i < M) {
-                rec[4 + i] = ok ? (uint32_t)(top[j] & 0xFFFFFFFFull) >> 1 : 0xFFFFFFFFu;
-                rec[4 + M + i] = ok ? __float_as_uint(gx_unkey((uint32_t)(top[j] >> 32), desc)) : 0u;
-            }
-            n_valid += (uint32_t)__popcll(__ballot(ok));           // n = valid entries among the first k
+        if (tid < M) {
+            const unsigned long long e = out[tid];
+            const bool ok = e != ~0ull && tid < m.k;
+            rec[4 + tid] = ok ? (uint32_t)(e & 0xFFFFFFFFull) >> 1 : 0xFFFFFFFFu;
+            rec[4 + M + tid] = ok ? __float_as_uint(gx_unkey((uint32_t)(e >> 32), desc)) : 0u;
+            n_valid = ok;
         }
-        if (lane == 0) {
-            rec[0] = n_valid; rec[1] = iters; rec[2] = m.evals; rec[3] = 0u;
+        if (n_valid) atomicAdd(&n_sh, n_valid);                   // n = valid entries among the first k
+        __syncthreads();
+        if (tid == 0) {
+            rec[0] = n_sh; rec[1] = iters; rec[2] = m.evals; rec[3] = 0u;
             mp->state = 0u;
             done[s] = 1u;                                          // (the host looks only after the step has completed)
         }
-    } else if (lane == 0) {
+    } else if (tid == 0) {
         mp->iters = iters;
         mp->fresh = 0u;
         mp->n_par = n_par;
         mp->n_tasks = n_tasks;
         mp->evals = m.evals + n_tasks;
     }
+}
+
+// ------------------------------------------------------------------------------------------ the step
+// One workgroup per slot runs the slot's whole step: distances of its tasks, merge, stop rule, next
+// extend.  Slots are independent of each other, so while one workgroup is in its latency-bound merge and
+// extend the others on the same compute unit keep the memory system busy with their row reads: the step
+// costs about what its row traffic costs, not the sum of its phases.
+template <int DT, int NCH>
+__global__ __launch_bounds__(GX_THREADS) void gx_step_kernel(GxDev D, uint32_t *__restrict__ done,
+                                                             uint32_t *__restrict__ rec_base, uint32_t rec_words)
+{
+    __shared__ float sdist[TRI_GRAPH_TASK_LIMIT];
+    const uint32_t s = blockIdx.x * D.ngroups + D.group;
+    if (s >= D.S) return;
+    GxMeta *mp = D.meta + s;
+    const GxMeta m = *mp;
+    if (m.state != 1u) return;                                    // (idle slot: masked)
+    // what the merge needs from memory is asked for now and arrives while the rows are being read
+    const unsigned long long old_e = threadIdx.x < D.M ? D.topm[(size_t)s * D.M + threadIdx.x] : ~0ull;
+    const uint32_t task_id = threadIdx.x < m.n_tasks ? D.tasks[(size_t)s * D.T + threadIdx.x] : TRI_GRAPH_PAD;
+    if (m.n_tasks) gx_distance_phase<DT, NCH>(D, s, m, sdist);
+    __syncthreads();
+    gx_merge_extend_phase(D, s, mp, m, sdist, old_e, task_id, done, rec_base, rec_words);
 }
 
 // ================================================================================== host side
@@ -574,18 +520,15 @@ int g_reap(tri_gpool *P, bool block, uint32_t *finished)
 }
 
 template <int DT>
-hipError_t g_launch_step(const GxDev &D, uint32_t nslots, hipStream_t stream, uint32_t *done, uint32_t *rec_base,
+hipError_t g_launch_step(const GxDev &D, uint32_t nblocks, hipStream_t stream, uint32_t *done, uint32_t *rec_base,
                          uint32_t rec_words)
 {
-    // capacities of the per-wavefront LDS arrays: whole chunks of 64 elements
-    const uint32_t Tcap = (std::max(D.p * D.degree, D.n_seeds) + 63u) / 64u * 64u, Mcap = (D.M + 63u) / 64u * 64u;
-    const uint32_t waves = GX_THREADS / 64;
-    const dim3 grid((nslots + waves - 1) / waves), block(GX_THREADS);
-    const size_t lds = (size_t)waves * (D.row_pitch + 12u * Tcap + 8u * Mcap);     // <= 4 * (4096 + 3072 + 2048) bytes
+    const dim3 grid(nblocks), block(GX_THREADS);
+    const size_t lds = D.row_pitch;
     switch (D.row_pitch / 256) {
-    case 2: hipLaunchKernelGGL((gx_step_kernel<DT, 2>), grid, block, lds, stream, D, done, rec_base, rec_words, Tcap, Mcap); break;
-    case 6: hipLaunchKernelGGL((gx_step_kernel<DT, 6>), grid, block, lds, stream, D, done, rec_base, rec_words, Tcap, Mcap); break;
-    default: hipLaunchKernelGGL((gx_step_kernel<DT, 0>), grid, block, lds, stream, D, done, rec_base, rec_words, Tcap, Mcap); break;
+    case 2: hipLaunchKernelGGL((gx_step_kernel<DT, 2>), grid, block, lds, stream, D, done, rec_base, rec_words); break;
+    case 6: hipLaunchKernelGGL((gx_step_kernel<DT, 6>), grid, block, lds, stream, D, done, rec_base, rec_words); break;
+    default: hipLaunchKernelGGL((gx_step_kernel<DT, 0>), grid, block, lds, stream, D, done, rec_base, rec_words); break;
     }
     return hipGetLastError();
 }
