@@ -150,6 +150,9 @@ def main():
         dst.copy_(src)                      # reads and writes copy_calibration_mib MiB each
         torch.cuda.synchronize()
         del src, dst
+    # context beside the vendor's peak: what a plain streaming read of the same base vectors achieves here
+    stream_gbs = tri.tri_stream_read_bandwidth(base_t, 3)
+    log(f"plain streaming read of the base ({base_t.numel() * base_t.element_size() / 1e9:.2f} GB): {stream_gbs:.0f} GB/s")
     # Settling, untimed and independent of --warmup: the first few hundred milliseconds under load run about
     # 7 % slower than the steady state (clocks ramping up), whatever is executed.
     log("settling 0.6 s under load")
@@ -268,6 +271,7 @@ def main():
                    "query_vectors": "host memory (PCIe-inclusive side measurement)" if args.host_queries else "device-resident"},
         "roofline": {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": MEASURED_TRAFFIC_BYTES.get(number),
+                     "streaming_read_GBs": round(stream_gbs, 1),
                      "kernel": "scan_wave_kernel (main launch)", "avg_launch_ms": round(scan_ms, 4),
                      "algorithmic_bytes_per_launch": int(unique_b), "tile_bytes_per_launch": int(tile_b),
                      "items_per_launch": int(kt.scan_items / max(kt.scan_launches, 1)), "row_bytes": row_bytes},

@@ -101,7 +101,7 @@ EXPORTS = ["tri_pool_workspace_bytes", "tri_pool_create", "tri_pool_destroy", "i
            "search_step", "search_poll", "search_poll_batch", "search_probes", "search_cancel", "search_sync",
            "search_run_stream", "search_set_policy", "search_get_policy", "tri_policy_split", "tri_policy_slack_order",
            "tri_policy_feedback", "search_set_feedback", "search_report_signals", "search_get_feedback",
-           "tri_pool_kernel_times", "tri_pool_set_profiling", "tri_pool_set_replay", "tri_last_error", "tri_version"]
+           "tri_pool_kernel_times", "tri_pool_set_profiling", "tri_pool_set_replay", "tri_stream_read_bandwidth", "tri_last_error", "tri_version"]
 
 
 def _load():
@@ -143,6 +143,7 @@ def _load():
     lib.tri_pool_kernel_times.argtypes = [vp, P(tri_kernel_times), ctypes.c_int]
     lib.tri_pool_set_profiling.argtypes = [vp, u32]
     lib.tri_pool_set_replay.argtypes = [vp, ctypes.c_int]
+    lib.tri_stream_read_bandwidth.argtypes = [vp, sz, vp, vp, u32, P(ctypes.c_double)]
     lib.tri_last_error.restype = ctypes.c_char_p
     lib.tri_version.restype = ctypes.c_char_p
     for name in EXPORTS:
@@ -192,6 +193,18 @@ def tri_pool_destroy(pool: int) -> None:
 
 def tri_pool_set_profiling(pool: int, flags: int) -> None:
     _check(_lib.tri_pool_set_profiling(ctypes.c_void_p(pool), flags), "tri_pool_set_profiling")
+
+
+def tri_stream_read_bandwidth(buf, repeats: int = 10) -> float:
+    """GB/s of a plain streaming read of the torch cuda tensor `buf` (on the current stream)."""
+    import torch
+    sink = torch.zeros(1, dtype=torch.int32, device=buf.device)
+    out = ctypes.c_double(0.0)
+    torch.cuda.synchronize()
+    _check(_lib.tri_stream_read_bandwidth(ctypes.c_void_p(buf.data_ptr()), buf.numel() * buf.element_size(),
+                                          ctypes.c_void_p(sink.data_ptr()), ctypes.c_void_p(torch.cuda.current_stream().cuda_stream),
+                                          repeats, ctypes.byref(out)), "tri_stream_read_bandwidth")
+    return float(out.value)
 
 
 def tri_pool_set_replay(pool: int, on: bool) -> None:

@@ -10,7 +10,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libtrinity_ivf.so")
-SOURCES = ["tri_api.hip", "coarse.hip", "scan.hip", "select.hip", "pack.hip", "build_kernels.hip", "feedback.hip", "graph_engine.hip"]
+SOURCES = ["tri_api.hip", "coarse.hip", "scan.hip", "select.hip", "pack.hip", "build_kernels.hip", "feedback.hip", "graph_engine.hip", "probe.hip"]
 FLAGS = ["-O3", "--offload-arch=gfx950", "-fPIC", "-std=c++17", "-Wall", "-Wno-unused-function",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
 
