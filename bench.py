@@ -44,7 +44,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=100)
     ap.add_argument("--warmup", type=int, default=10)
-    ap.add_argument("--workload", default="config4", choices=["config4", "config2", "config1", "config3", "graph"])
+    ap.add_argument("--workload", default="config4", choices=["config4", "config2", "config1", "config3", "graph", "graph-stream"])
     ap.add_argument("--graph-n", type=int, default=1_000_000, help="graph workload: database rows")
     ap.add_argument("--graph-slots", type=int, default=8192, help="graph workload: requests advanced per step")
     ap.add_argument("--graph-topm", type=int, default=128, help="graph workload: length of a request's candidate list")
@@ -79,6 +79,8 @@ def main():
         sys.exit(3)
     if args.workload == "graph":
         return graph_bench(args, tri, torch)
+    if args.workload == "graph-stream":
+        return graph_stream_bench(args, tri, torch)
     number = int(args.workload[-1])
     if number == 3:
         return stream_bench(args, tri, workloads, torch)
@@ -527,6 +529,67 @@ def graph_bench(args, tri, torch):
                              "partly cache-assisted"},
         "cpu_baseline": cpu,
         "wall_s_total": round(time.time() - t_start, 1),
+    }
+    pool.close()
+    print(json.dumps(result), flush=True)
+
+
+def graph_stream_bench(args, tri, torch):
+    """The graph engine under arrivals (Sec. 3.2's claim: continuous batching against batches that must drain):
+    the graph workload's index, --stream-queries host-resident queries, first all offered at once (saturation),
+    then Poisson arrivals at 0.5 x and 0.8 x of the continuous scheme's saturation rate -- each with continuous
+    batching and with static batches (a group of slots admits only when all of it has finished)."""
+    import graph_inputs
+    import workloads
+    from paper_2512_02281_amd import graph as tg
+    t_start = time.time()
+    n, dim, latent, D, n_rand, M, p, iters, k = args.graph_n, 768, 12, 32, 8, args.graph_topm, args.graph_parents, 64, 10
+    S, nq = args.graph_slots, args.stream_queries
+    log(f"workload graph-stream: generating {n} x {dim} fp16, its degree-{D} neighbour list and {nq} queries (untimed)")
+    X, Z = graph_inputs.make_points(n, dim, latent, np.float16, graph_inputs.SEED_POINTS, device="cuda")
+    Qv, _ = graph_inputs.make_points(nq, dim, latent, np.float16, graph_inputs.SEED_QUERIES, device="cuda")
+    G = graph_inputs.make_graph(Z, D, n_rand, graph_inputs.SEED_EDGES, block=1024).to(torch.int32)
+    seeds = graph_inputs.entry_points(n, args.graph_seeds)
+    Qh = np.ascontiguousarray(Qv.cpu().numpy())
+    torch.cuda.synchronize()
+    pool = tg.GraphPool(X, G, seeds, tri.TRI_F16, slots=S, topm=M, parents=p, max_iters=iters, max_outstanding=nq + S,
+                        groups=args.graph_groups, own_stream=True)
+    pct = lambda a: [round(float(np.percentile(a, x)), 3) for x in (50, 95, 99)]
+
+    def run(arrival, static, label):
+        ids, dist, n_out, done_s, st = pool.run_stream(Qh, arrival, k, tri.TRI_IP, static_batches=static)
+        lat = (done_s - arrival) * 1e3
+        r = {"label": label, "batching": "static batches" if static else "continuous",
+             "offered_qps": None if arrival[-1] == 0 else round(nq / arrival[-1], 1),
+             "throughput_qps": round(nq / st.wall_s, 1), "steps": int(st.steps),
+             "mean_running_slots": round(st.running / max(st.steps, 1), 1), "longest_queue": int(st.max_pending),
+             "latency_ms_p50_p95_p99": pct(lat)}
+        log(str(r))
+        return r, ids
+
+    log("warm-up")
+    run(np.zeros(nq), False, "warm-up")
+    runs = []
+    sat, ids_ref = run(np.zeros(nq), False, "all queries offered at t = 0")
+    runs.append(sat)
+    r, ids_s = run(np.zeros(nq), True, "all queries offered at t = 0")
+    runs.append(r)
+    assert np.array_equal(ids_ref, ids_s), "the batching scheme changed a result"
+    for frac in (0.5, 0.8):
+        arr = workloads.poisson_arrivals(nq, frac * sat["throughput_qps"], 4005)
+        for static in (False, True):
+            r, ids_x = run(arr, static, f"Poisson arrivals at {frac} x the continuous scheme's saturation rate")
+            runs.append(r)
+            assert np.array_equal(ids_ref, ids_x), "the batching scheme changed a result"
+    result = {
+        "metric": "queries/sec at recall@k>=0.9 (1 GPU) + list-scan HBM GB/s as % of peak",
+        "value": sat["throughput_qps"], "unit": "queries/s", "n_gpus": 1, "steps": sat["steps"], "warmup": 1,
+        "ms_per_step": round(1e3 * nq / sat["throughput_qps"] / max(sat["steps"], 1), 4), "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": "f16", "data": "synthetic",
+        "config": {"workload": f"graph engine stream: {nq} host-resident queries over {n} x {dim} fp16 (degree {D}, topM {M}, "
+                               f"{p} parents per extend, k {k}), {S} slots in {args.graph_groups} groups",
+                   "query_vectors": "host memory (copied at arrival, read by the admitting step)"},
+        "roofline": None, "stream": runs, "cpu_baseline": None, "wall_s_total": round(time.time() - t_start, 1),
     }
     pool.close()
     print(json.dumps(result), flush=True)

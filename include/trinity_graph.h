@@ -105,6 +105,25 @@ int graph_poll(tri_gpool *pool, const tri_ticket *t /*[host] n*/, uint32_t n, ui
                uint32_t *n_out /*[host] n*/, int64_t *ids /*[host] n*stride*/, float *dist /*[host] n*stride*/,
                uint32_t *iters /*[host] n or NULL*/, uint32_t *evals /*[host] n or NULL*/, int *status /*[host] n*/);
 
+/* The serving loop of Sec. 3.2 as one native call, for measuring a stream: query i (vecs [host]: n rows, row
+ * pitch pitch_bytes) is queued when arrival_s[i] seconds have passed since the call began, graph_step is
+ * called whenever something runs or waits, and every result is stored as soon as its step has been
+ * collected: row i of ids / dist (stride entries, >= every k) and n_out[i] as graph_poll fills them,
+ * done_s[i] = seconds from the beginning of the call until the result was on the host (latency of query i =
+ * done_s[i] - arrival_s[i]).  static_batches != 0 runs the scheme continuous batching replaces: a group of
+ * slots admits new requests only when every request of the group has finished.  The pool must be idle and
+ * have n free tickets; arrival_s must not decrease. */
+typedef struct {
+    double wall_s;         /* duration of the call                                                      */
+    uint64_t steps;        /* steps enqueued                                                            */
+    uint64_t running;      /* occupied slots (as the host knows) summed over those steps                */
+    uint64_t max_pending;  /* longest the waiting queue ever was                                        */
+} tri_graph_stream_stats;
+int graph_run_stream(tri_gpool *pool, const void *vecs /*[host]*/, uint64_t pitch_bytes, const double *arrival_s /*[host] n*/,
+                     uint32_t n, const uint32_t *k, const uint32_t *metric, const uint32_t *klass /*[host] n or NULL*/,
+                     int static_batches, uint32_t stride, uint32_t *n_out /*[host] n*/, int64_t *ids /*[host] n*stride*/,
+                     float *dist /*[host] n*stride*/, double *done_s /*[host] n*/, tri_graph_stream_stats *stats /*[host] out or NULL*/);
+
 /* Block until every enqueued step has completed and collect their results. */
 int graph_sync(tri_gpool *pool);
 

@@ -422,6 +422,13 @@ struct tri_gpool {
     uint64_t step_seq = 0;
     GStep ring[GRING];
     tri_graph_times times{};
+    // graph_run_stream: finished results go straight to the caller's arrays
+    struct Sink {
+        std::vector<uint32_t> q_of_ticket;
+        uint32_t *n_out; int64_t *ids; float *dist; double *done_s;
+        uint32_t stride; int64_t t0_ns; uint32_t delivered;
+    } *sink = nullptr;
+    bool static_batches = false;      // admit into a group of slots only when the whole group is idle
 };
 
 namespace {
@@ -498,9 +505,25 @@ int g_reap(tri_gpool *P, bool block, uint32_t *finished)
             GTicket &t = P->tickets[ti];
             t.n_out = rec[0]; t.iters = rec[1]; t.evals = rec[2];
             tasks += t.evals;
-            memcpy(&P->res_ids[(size_t)ti * M], rec + 4, (size_t)t.n_out * 4);
-            memcpy(&P->res_score[(size_t)ti * M], rec + 4 + M, (size_t)t.n_out * 4);
-            t.state = G_DONE;
+            if (P->sink) {
+                tri_gpool::Sink &K = *P->sink;
+                const uint32_t qi = K.q_of_ticket[ti];
+                int64_t *oi = K.ids + (size_t)qi * K.stride;
+                float *od = K.dist + (size_t)qi * K.stride;
+                for (uint32_t j = 0; j < t.n_out; ++j) { oi[j] = (int64_t)rec[4 + j]; od[j] = __builtin_bit_cast(float, rec[4 + M + j]); }
+                const float pad = t.metric == TRI_L2 ? __builtin_inff() : -__builtin_inff();
+                for (uint32_t j = t.n_out; j < t.k; ++j) { oi[j] = -1; od[j] = pad; }
+                K.n_out[qi] = t.n_out;
+                K.done_s[qi] = (double)(gnow_ns() - K.t0_ns) * 1e-9;
+                ++K.delivered;
+                t.state = G_FREE;
+                ++t.gen;
+                P->free_tickets.push_back(ti);
+            } else {
+                memcpy(&P->res_ids[(size_t)ti * M], rec + 4, (size_t)t.n_out * 4);
+                memcpy(&P->res_score[(size_t)ti * M], rec + 4 + M, (size_t)t.n_out * 4);
+                t.state = G_DONE;
+            }
             R->free_slots.push_back(slot);
             --R->n_running;
             --P->n_running;
@@ -699,11 +722,21 @@ extern "C" int graph_submit(tri_gpool *P, const void *vecs, int on_device, uint6
     return TRI_OK;
 }
 
+namespace {
+int g_step_locked(tri_gpool *P, tri_graph_step_stats *st);
+}
+
 extern "C" int graph_step(tri_gpool *P, tri_graph_step_stats *st)
 {
     if (!P) return tri_fail(TRI_EINVAL, "pool is NULL");
     std::lock_guard<std::mutex> lk(P->mu);
     GHIP(hipSetDevice(P->device));
+    return g_step_locked(P, st);
+}
+
+namespace {
+int g_step_locked(tri_gpool *P, tri_graph_step_stats *st)
+{
     tri_graph_step_stats stats{};
     int rc = g_reap(P, false, &stats.finished);
     if (rc) return rc;
@@ -720,7 +753,8 @@ extern "C" int graph_step(tri_gpool *P, tri_graph_step_stats *st)
     GxHdr *hdr = (GxHdr *)R.up_host;
     GxNewDesc *desc = (GxNewDesc *)(R.up_host + sizeof(GxHdr));
     uint32_t n_new = 0;
-    for (int klass = 0; klass < 2; ++klass) {
+    const bool may_admit = !P->static_batches || R.n_running == 0;
+    for (int klass = 0; klass < 2 && may_admit; ++klass) {
         std::deque<uint32_t> &Q = P->pending[klass];
         while (!Q.empty() && !R.free_slots.empty()) {
             const uint32_t ti = Q.front();
@@ -768,6 +802,68 @@ extern "C" int graph_step(tri_gpool *P, tri_graph_step_stats *st)
     R.seq = stats.step;
     if (st) *st = stats;
     return TRI_OK;
+}
+
+}  // namespace
+
+// The serving loop of Sec. 3.2 as one native call (arrivals join at the next step of a group with a free slot,
+// finished requests leave at once), or -- static_batches -- the scheme it replaces: a group of slots takes new
+// requests only when all of its requests have finished.
+extern "C" int graph_run_stream(tri_gpool *P, const void *vecs, uint64_t pitch_bytes, const double *arrival_s, uint32_t n,
+                                const uint32_t *k, const uint32_t *metric, const uint32_t *klass, int static_batches,
+                                uint32_t stride, uint32_t *n_out, int64_t *ids, float *dist, double *done_s,
+                                tri_graph_stream_stats *stats)
+{
+    if (!P || (n && (!vecs || !arrival_s || !k || !metric || !n_out || !ids || !dist || !done_s)))
+        return tri_fail(TRI_EINVAL, "NULL argument");
+    const size_t es = P->D.dtype == TRI_F16 ? 2 : 4;
+    if (pitch_bytes < (uint64_t)P->D.dim * es || pitch_bytes % es) return tri_fail(TRI_EINVAL, "pitch_bytes too small or not a multiple of the element size");
+    for (uint32_t i = 0; i < n; ++i) {
+        if (k[i] == 0 || k[i] > P->cfg.topm || k[i] > stride) return tri_fail(TRI_EINVAL, "k must be 1..min(topm, stride) (query %u has %u)", i, k[i]);
+        if (metric[i] != TRI_L2 && metric[i] != TRI_IP) return tri_fail(TRI_EINVAL, "metric must be TRI_L2 or TRI_IP");
+        if (klass && klass[i] != TRI_CLASS_HIGH && klass[i] != TRI_CLASS_LOW) return tri_fail(TRI_EINVAL, "klass must be TRI_CLASS_HIGH or TRI_CLASS_LOW");
+        if (i && arrival_s[i] < arrival_s[i - 1]) return tri_fail(TRI_EINVAL, "arrival times must not decrease");
+    }
+    std::lock_guard<std::mutex> lk(P->mu);
+    GHIP(hipSetDevice(P->device));
+    if (P->n_running || !P->pending[0].empty() || !P->pending[1].empty()) return tri_fail(TRI_EINVAL, "the pool must be idle");
+    if (P->free_tickets.size() < n) return tri_fail(TRI_ENOMEM, "max_outstanding leaves %zu free tickets, the stream has %u queries", P->free_tickets.size(), n);
+    tri_gpool::Sink K;
+    try { K.q_of_ticket.assign(P->tickets.size(), 0); } catch (const std::bad_alloc &) { return tri_fail(TRI_ENOMEM, "out of host memory"); }
+    K.n_out = n_out; K.ids = ids; K.dist = dist; K.done_s = done_s; K.stride = stride; K.delivered = 0;
+    K.t0_ns = gnow_ns();
+    P->sink = &K;
+    P->static_batches = static_batches != 0;
+    tri_graph_stream_stats S{};
+    uint32_t next = 0;
+    int rc = TRI_OK;
+    while (K.delivered < n && rc == TRI_OK) {
+        const double now = (double)(gnow_ns() - K.t0_ns) * 1e-9;
+        while (next < n && arrival_s[next] <= now) {              // queue what has arrived
+            const uint32_t ti = P->free_tickets.back();
+            P->free_tickets.pop_back();
+            GTicket &t = P->tickets[ti];
+            t.state = G_PENDING;
+            t.k = k[next]; t.metric = metric[next]; t.klass = klass ? klass[next] : (uint32_t)TRI_CLASS_LOW;
+            memcpy(P->qstore + (size_t)ti * P->D.row_pitch, (const uint8_t *)vecs + (size_t)next * pitch_bytes, (size_t)P->D.dim * es);
+            t.dev_vec = P->qstore_dev + (size_t)ti * P->D.row_pitch;
+            K.q_of_ticket[ti] = next;
+            P->pending[t.klass].push_back(ti);
+            ++next;
+        }
+        const uint64_t waiting = P->pending[0].size() + P->pending[1].size();
+        S.max_pending = std::max<uint64_t>(S.max_pending, waiting);
+        if (P->n_running == 0 && waiting == 0) continue;          // nothing to do until the next arrival
+        tri_graph_step_stats st{};
+        rc = g_step_locked(P, &st);
+        if (rc == TRI_OK && (st.running || st.admitted)) { S.steps += 1; S.running += st.running; }
+    }
+    if (rc == TRI_OK) rc = g_reap(P, true, nullptr);
+    S.wall_s = (double)(gnow_ns() - K.t0_ns) * 1e-9;
+    P->sink = nullptr;
+    P->static_batches = false;
+    if (stats) *stats = S;
+    return rc;
 }
 
 extern "C" int graph_poll(tri_gpool *P, const tri_ticket *tk, uint32_t n, uint32_t stride, uint32_t *n_out, int64_t *ids,

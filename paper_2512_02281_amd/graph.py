@@ -12,7 +12,7 @@ from . import (TRI_CLASS_LOW, TRI_EAGAIN, TRI_F16, TRI_F32, TRI_FLAG_PROFILE, TR
                tri_last_error)
 
 GRAPH_EXPORTS = ["graph_pool_bytes", "graph_pool_create", "graph_pool_destroy", "graph_submit", "graph_step",
-                 "graph_poll", "graph_sync", "graph_kernel_times"]
+                 "graph_poll", "graph_sync", "graph_kernel_times", "graph_run_stream"]
 TRI_GRAPH_TOPM_LIMIT = 256
 TRI_GRAPH_TASK_LIMIT = 256
 TRI_GRAPH_PAD = 0xFFFFFFFF
@@ -34,6 +34,11 @@ class tri_graph_times(ctypes.Structure):
                 ("row_bytes", ctypes.c_uint32), ("pad_", ctypes.c_uint32)]
 
 
+class tri_graph_stream_stats(ctypes.Structure):
+    _fields_ = [("wall_s", ctypes.c_double), ("steps", ctypes.c_uint64), ("running", ctypes.c_uint64),
+                ("max_pending", ctypes.c_uint64)]
+
+
 def _declare():
     vp, u32, u64, sz = ctypes.c_void_p, ctypes.c_uint32, ctypes.c_uint64, ctypes.c_size_t
     P = ctypes.POINTER
@@ -44,6 +49,8 @@ def _declare():
     _lib.graph_step.argtypes = [vp, P(tri_graph_step_stats)]
     _lib.graph_poll.argtypes = [vp, vp, u32, u32, vp, vp, vp, vp, vp, vp]
     _lib.graph_sync.argtypes = [vp]
+    _lib.graph_run_stream.argtypes = [vp, vp, u64, vp, u32, vp, vp, vp, ctypes.c_int, u32, vp, vp, vp, vp,
+                                      P(tri_graph_stream_stats)]
     _lib.graph_kernel_times.argtypes = [vp, P(tri_graph_times), ctypes.c_int]
     for name in GRAPH_EXPORTS:
         getattr(_lib, name).restype = ctypes.c_int
@@ -153,6 +160,26 @@ class GraphPool:
         assert np.all(status == TRI_OK), status[status != 0][:5]
         self._keep.clear()
         return ids, dist, n_out, iters, evals, steps
+
+    def run_stream(self, vecs: np.ndarray, arrival_s: np.ndarray, k, metric, klass=None, static_batches: bool = False):
+        """Drive the pool through a stream of host queries.  Returns (ids, dist, n_out, done_s, stats)."""
+        n = int(vecs.shape[0])
+        vecs = np.ascontiguousarray(vecs)
+        arrival_s = np.ascontiguousarray(arrival_s, dtype=np.float64)
+        k = np.ascontiguousarray(np.broadcast_to(np.asarray(k, dtype=np.uint32), (n,)))
+        metric = np.ascontiguousarray(np.broadcast_to(np.asarray(metric, dtype=np.uint32), (n,)))
+        kl = None if klass is None else np.ascontiguousarray(np.broadcast_to(np.asarray(klass, dtype=np.uint32), (n,)))
+        stride = int(k.max()) if n else 1
+        ids = np.full((n, stride), -1, dtype=np.int64)
+        dist = np.full((n, stride), np.nan, dtype=np.float32)
+        n_out = np.zeros(n, dtype=np.uint32)
+        done_s = np.zeros(n, dtype=np.float64)
+        st = tri_graph_stream_stats()
+        _check(_lib.graph_run_stream(ctypes.c_void_p(self.handle), _ptr(vecs), vecs.strides[0] if n else 0, _np_ptr(arrival_s), n,
+                                     _np_ptr(k), _np_ptr(metric), _np_ptr(kl) if kl is not None else None,
+                                     1 if static_batches else 0, stride, _np_ptr(n_out), _np_ptr(ids), _np_ptr(dist),
+                                     _np_ptr(done_s), ctypes.byref(st)), "graph_run_stream")
+        return ids, dist, n_out, done_s, st
 
     def kernel_times(self, reset: bool = False) -> tri_graph_times:
         t = tri_graph_times()

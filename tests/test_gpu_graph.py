@@ -198,6 +198,40 @@ def test_full_size_in_the_benchmark_configuration():
     assert same >= 0.97 * sel.size
 
 
+def test_serving_loop_continuous_and_static_batches():
+    """graph_run_stream: timed arrivals, results delivered as steps complete, with continuous batching and with
+    static batches -- identical to the step-by-step results (which equal the oracle's, tested above) either way;
+    every latency is positive; static batches need at least as many steps."""
+    tri, tg = _lib()
+    n, nq, dim, D, M, p, iters = 20_000, 400, 128, 16, 32, 2, 30
+    Xt, Z = graph_inputs.make_points(n, dim, 8, np.float32, graph_inputs.SEED_POINTS, integer=True)
+    Qt, _ = graph_inputs.make_points(nq, dim, 8, np.float32, graph_inputs.SEED_QUERIES, integer=True)
+    X, Q, G = Xt.numpy(), Qt.numpy(), graph_inputs.make_graph(Z, D, 4, graph_inputs.SEED_EDGES).numpy().astype(np.uint32)
+    seeds = graph_inputs.entry_points(n, 16)
+    k = np.random.default_rng(2).integers(1, M + 1, size=nq).astype(np.uint32)
+    metric = (np.arange(nq) % 2).astype(np.uint32)
+    arrival = np.cumsum(np.random.default_rng(3).exponential(20e-6, size=nq))        # about 50,000 arrivals a second
+    with tg.GraphPool(X, G, seeds, tri.TRI_F32, slots=48, topm=M, parents=p, max_iters=iters, max_outstanding=512,
+                      groups=2) as pool:
+        ref = pool.run_all(Q, k, metric)
+        steps = {}
+        for static in (False, True):
+            ids, dist, n_out, done_s, st = pool.run_stream(Q, arrival, k, metric, static_batches=static)
+            for i in range(nq):
+                kk = int(k[i])
+                assert np.array_equal(ids[i, :kk], ref[0][i, :kk]) and int(n_out[i]) == int(ref[2][i])
+                assert np.array_equal(dist[i, :kk].view(np.uint32), ref[1][i, :kk].view(np.uint32))
+            assert np.all(done_s > arrival) and st.wall_s >= done_s.max() - 1e-9
+            steps[static] = int(st.steps)
+            _say(f"stream, static batches {static}: {st.steps} steps, p50 latency {np.percentile(done_s - arrival, 50) * 1e3:.3f} ms, "
+                 f"p99 {np.percentile(done_s - arrival, 99) * 1e3:.3f} ms")
+        assert steps[True] >= steps[False]
+        again = pool.run_all(Q, k, metric)                              # the pool is usable step by step afterwards
+        assert np.array_equal(again[0], ref[0])
+        with pytest.raises(tri.TriError):
+            pool.run_stream(Q, arrival[::-1].copy(), k, metric)          # arrival times must not decrease
+
+
 def test_argument_errors_and_empty_steps():
     tri, tg = _lib()
     X = np.arange(32, dtype=np.float32).reshape(16, 2)
