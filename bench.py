@@ -344,6 +344,11 @@ def stream_bench(args, tri, workloads, torch):
     for frac in (0.5, 0.8):
         runs.append(run(workloads.poisson_arrivals(n, frac * t_sat, 4003), f"Poisson arrivals at {frac} x saturation")[0])
     runs.append(run(workloads.poisson_arrivals(n, 1.0e5, 4003), "Poisson arrivals at 100,000 / s")[0])
+    # the scheme continuous batching replaces (Sec. 3.2): a batch must drain before the next is admitted
+    runs.append(run(np.zeros(n), "closed loop, static batches", static_batches=True)[0])
+    for frac in (0.5, 0.8):
+        runs.append(run(workloads.poisson_arrivals(n, frac * t_sat, 4003), f"Poisson arrivals at {frac} x saturation, static batches",
+                        static_batches=True)[0])
     # the step-boundary policy (Sec. 3.3) where slots are scarce -- a burst, everything offered at once:
     # one queue, two classes with the cache lookups first, a reserved share, and least-slack order with
     # a budget on the cache lookups

@@ -244,6 +244,10 @@ typedef struct {
                                     step when its slot table can be filled, or when the oldest waiting
                                     query has waited this long (0, default: at once) ...              */
     double flush_timeout_high_s; /* ... or when the oldest waiting high-class query has waited this long */
+    uint32_t static_batches;     /* != 0: for comparison, the scheme continuous batching replaces -- queries are
+                                    admitted only when no query is running, so a batch drains before the next
+                                    starts (0, default: arrivals join at every step boundary, Sec. 3.2)       */
+    uint32_t pad_;
 } tri_policy;
 int search_set_policy(tri_pool *pool, const tri_policy *policy /*[host]*/);
 /* The policy in force and T, the mean step duration the slack order uses (seconds; 0 before the

@@ -75,7 +75,8 @@ class tri_kernel_times(ctypes.Structure):
 
 class tri_policy(ctypes.Structure):
     _fields_ = [("high_share", ctypes.c_float), ("order_high", ctypes.c_uint32),
-                ("flush_timeout_s", ctypes.c_double), ("flush_timeout_high_s", ctypes.c_double)]
+                ("flush_timeout_s", ctypes.c_double), ("flush_timeout_high_s", ctypes.c_double),
+                ("static_batches", ctypes.c_uint32), ("pad_", ctypes.c_uint32)]
 
 
 class tri_feedback_cfg(ctypes.Structure):
@@ -360,8 +361,8 @@ def search_sync(pool: int) -> None:
 
 
 def search_set_policy(pool: int, high_share: float = 1.0, order_high: int = TRI_ORDER_FIFO,
-                      flush_timeout_s: float = 0.0, flush_timeout_high_s: float = 0.0) -> None:
-    pol = tri_policy(high_share, order_high, flush_timeout_s, flush_timeout_high_s)
+                      flush_timeout_s: float = 0.0, flush_timeout_high_s: float = 0.0, static_batches: bool = False) -> None:
+    pol = tri_policy(high_share, order_high, flush_timeout_s, flush_timeout_high_s, 1 if static_batches else 0, 0)
     _check(_lib.search_set_policy(ctypes.c_void_p(pool), ctypes.byref(pol)), "search_set_policy")
 
 
@@ -374,7 +375,8 @@ def search_get_policy(pool: int):
 
 def tri_policy_feedback(cfg: tri_feedback_cfg, signals: tri_feedback_signals, policy: tri_policy):
     """One period of the control loop: returns (new tri_policy, bit mask of the rules that applied)."""
-    out = tri_policy(policy.high_share, policy.order_high, policy.flush_timeout_s, policy.flush_timeout_high_s)
+    out = tri_policy(policy.high_share, policy.order_high, policy.flush_timeout_s, policy.flush_timeout_high_s,
+                     policy.static_batches, 0)
     rules = ctypes.c_uint32(0)
     _check(_lib.tri_policy_feedback(ctypes.byref(cfg), ctypes.byref(signals), ctypes.byref(out), ctypes.byref(rules)),
            "tri_policy_feedback")

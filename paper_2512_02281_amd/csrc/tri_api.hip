@@ -180,7 +180,7 @@ struct tri_pool {
     std::vector<uint32_t> run_order[2];   // running slots per class, in admission order (with the admission number
     std::vector<uint64_t> run_seq[2];     //   each had then: a slot number alone could be a later occupant)
     // scheduling policy (Sec. 3.3) and the measured mean step duration its slack order uses
-    tri_policy policy{1.0f, TRI_ORDER_FIFO, 0.0, 0.0};
+    tri_policy policy{1.0f, TRI_ORDER_FIFO, 0.0, 0.0, 0u, 0u};
     double mean_step_s = 0.0;
     int64_t last_done_ns = 0;
     // control loop of Sec. 3.3 (search_set_feedback)
@@ -1046,7 +1046,8 @@ extern "C" int search_step(tri_pool *P, tri_step_stats *st)
     uint32_t n_distinct = 0;
     {
         uint32_t take[2] = {0, 0};
-        tri_policy_split((uint32_t)P->free_slots.size(), (uint32_t)P->pending[0].size(), (uint32_t)P->pending[1].size(),
+        const bool hold = P->policy.static_batches && P->n_running > 0;       // (a batch must drain before the next starts)
+        tri_policy_split(hold ? 0u : (uint32_t)P->free_slots.size(), (uint32_t)P->pending[0].size(), (uint32_t)P->pending[1].size(),
                          P->policy.high_share, &take[0], &take[1]);
         std::deque<uint32_t> &H = P->pending[TRI_CLASS_HIGH];
         if (P->policy.order_high == TRI_ORDER_SLACK && take[0] && H.size() > 1) {

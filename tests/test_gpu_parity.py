@@ -499,6 +499,30 @@ def test_control_loop_moves_the_policy_inside_the_pool():
             tri.search_report_signals(pool.handle, 1.5, 0.0)
 
 
+def test_static_batches_drain_before_admitting():
+    """tri_policy.static_batches (the scheme continuous batching replaces, kept for comparison): no query is
+    admitted while one is running; results are those of continuous batching."""
+    tri = harness.lib()
+    cfg = workloads.CONFIGS[0].scaled(n_base=8_000, n_components=32, nlist=32, n_queries=40)
+    base, queries, rows = workloads.make_config01(cfg)
+    nprobe = np.where(np.arange(40) % 5 == 0, 16, 4).astype(np.uint32)         # some queries need 4 steps, most 1
+    with harness.default_pool(tri, slots=8, lists_per_query_step=4, max_dim=cfg.dim, max_outstanding=512) as pool:
+        idx = _build_f32(tri, pool, cfg, base, rows)
+        q = tri.make_queries(idx, queries, 10, nprobe, tri.TRI_L2)
+        ref = harness.run_all(tri, pool, q)
+        tri.search_set_policy(pool.handle, static_batches=True)
+        ids, dist, n_out, probes, stats = harness.run_all(tri, pool, q)
+        tri.search_set_policy(pool.handle)
+        assert np.array_equal(ids, ref[0]) and np.array_equal(dist.view(np.uint32), ref[1].view(np.uint32))
+        # (admitted, retired, running, items) per step: admissions only into an empty table, 8 at a time
+        running_before = 0
+        for admitted, retired, running, items in stats:
+            assert admitted == 0 or (running_before == 0 and admitted == min(8, admitted))
+            running_before = running - retired
+        assert len(stats) > len(ref[4])                                   # the drain costs steps
+        assert sum(a for a, _, _, _ in stats) == 40
+
+
 def test_scheduling_policy_reservation_slack_and_flush():
     """The step-boundary policy of the paper's Sec. 3.3 on the GPU path: the reserved share splits the free
     slots between the classes, the slack order admits the most urgent high-class query first, flush
