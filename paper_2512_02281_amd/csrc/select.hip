@@ -570,6 +570,54 @@ __global__ __launch_bounds__(TRI_SEL_THREADS) void coarse_select_kernel(
         for (int u = 0; u < CSEL_PER; ++u)                         // (all-ones: padding, ignored below)
             key[u] = u * TRI_SEL_THREADS + tid < nlist ? sel_key(__uint_as_float(key[u]), d.metric) : 0xFFFFFFFFu;
         if (tid == 0) sh.cnt = 0;
+        if (d.nprobe <= TRI_SEL_THREADS) {
+            // A bound without a histogram: every thread's best key is one of 256 distinct elements, so the
+            // nprobe-th smallest of those 256 is not better than the nprobe-th best of the whole row.  With 64
+            // keys per thread it admits nprobe and a few dozen more; those are compacted and sorted exactly.
+            uint32_t best = 0xFFFFFFFFu;
+#pragma unroll
+            for (int u = 0; u < CSEL_PER; ++u) best = key[u] < best ? key[u] : best;
+            uint32_t *mins = (uint32_t *)sh.pool;
+            mins[tid] = best;
+            __syncthreads();
+            uint32_t rank = 0;
+            for (uint32_t j = 0; j < TRI_SEL_THREADS; j += 4) {
+                const uint4 y = *(const uint4 *)(mins + j);
+                rank += (y.x < best || (y.x == best && j < tid)) + (y.y < best || (y.y == best && j + 1 < tid)) +
+                        (y.z < best || (y.z == best && j + 2 < tid)) + (y.w < best || (y.w == best && j + 3 < tid));
+            }
+            if (rank == d.nprobe - 1) sh.tmax = best;
+            __syncthreads();
+            const uint32_t bound = sh.tmax;
+            __syncthreads();                                          // (mins is read: the pool may be written)
+            if (bound != 0xFFFFFFFFu) {
+                uint32_t mine = 0;
+#pragma unroll
+                for (int u = 0; u < CSEL_PER; ++u) mine += key[u] <= bound;
+                const uint32_t c_le = sel_block_scan_incl(mine, sh.wave_tot);
+                if (tid == TRI_SEL_THREADS - 1) sh.count = c_le;
+                __syncthreads();
+                const uint32_t total = sh.count;
+                if (total <= SEL_SMALL) {
+                    uint32_t pos = c_le - mine;                       // (this thread's place among the admitted)
+#pragma unroll
+                    for (int u = 0; u < CSEL_PER; ++u)
+                        if (key[u] <= bound) sh.small[pos++] = ((uint64_t)key[u] << 32) | (uint32_t)(u * TRI_SEL_THREADS + tid);
+                    __syncthreads();
+                    const uint64_t *best_of;
+                    if (total <= SEL_RANK_MAX) {
+                        sel_rank_sort(sh.small, total, sh.pool);
+                        best_of = sh.pool;
+                    } else {
+                        sel_bitonic(sh.small, total);
+                        best_of = sh.small;
+                    }
+                    for (uint32_t i = tid; i < d.nprobe; i += TRI_SEL_THREADS) dst[i] = (uint32_t)(best_of[i] & 0xFFFFFFFFu);
+                    return;                                           // (uniform: total comes from shared memory)
+                }
+            }
+            __syncthreads();
+        }
         uint32_t kmin, lo = 0xFFFFFFFFu, hi = 0u;
 #pragma unroll
         for (int u = 0; u < CSEL_PER; ++u)
