@@ -51,6 +51,9 @@ def main():
     ap.add_argument("--graph-parents", type=int, default=4, help="graph workload: parents expanded per extend")
     ap.add_argument("--graph-groups", type=int, default=3, help="graph workload: slot groups stepped in turn (1..4)")
     ap.add_argument("--graph-seeds", type=int, default=64, help="graph workload: entry points")
+    ap.add_argument("--queries-per-step", type=int, default=0,
+                    help="config1/2/4: queries per batch instead of the configuration's own number (a side measurement of how "
+                         "the path scales when more queries share each list read; never the headline value)")
     ap.add_argument("--stream-queries", type=int, default=100_000, help="config3: queries in the stream")
     ap.add_argument("--cpu-sample", type=int, default=-1, help="queries timed on the CPU oracle (0 = skip)")
     ap.add_argument("--recall-sample", type=int, default=64, help="queries checked against exact search (graph workload: 4 x as many)")
@@ -85,6 +88,9 @@ def main():
     if number == 3:
         return stream_bench(args, tri, workloads, torch)
     cfg = workloads.CONFIGS[number]
+    if args.queries_per_step:
+        import dataclasses
+        cfg = dataclasses.replace(cfg, n_queries=args.queries_per_step)
     t_start = time.time()
     log(f"workload {cfg.name}: generating {cfg.n_base} x {cfg.dim}")
     if number == 1:
