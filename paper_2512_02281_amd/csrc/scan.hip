@@ -18,7 +18,7 @@
 //    scores written densely; a small kernel then sets each query's threshold to the k-th best of
 //    its sample (and running top-k).  A k-th best of a SUBSET of the candidates can only be worse
 //    than the k-th best of all of them, so nothing that belongs to the top-k is beyond it.
-//  * main launch (FILTER = true): every other vector is scored (the sample was the first block of
+//  * main launch (FILTER = true): every other vector is scored (the sample was the first two blocks of
 //    each list; what passed of it already heads the candidate regions, put there by the threshold
 //    kernel), and only the scores not worse than the query's threshold are appended, as (score bits,
 //    position in list) pairs, to the (query, chunk) region of the candidate buffer.  The result is
@@ -199,9 +199,9 @@ __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(1, 1))) void
             // (sized to whole blocks: a 16-byte load never straddles its end; the norm array has a block of slack)
             const __amdgpu_buffer_rsrc_t nrs =
                 __builtin_amdgcn_make_buffer_rsrc((void *)tl.vnorm_addr, 0, nblocks * TRI_VB * 4u, SCAN_BUF_FLAGS);
-            // (main launch: the first block of a list was scored by the sample launch, and what passed of it
-            // already heads the candidate regions; the scan of a list's first chunk starts at its second block)
-            const uint32_t b0 = FILTER && tl.vec_begin == 0 ? 1u : 0u;
+            // (main launch: the first TRI_SAMPLE_VECS vectors of a list were scored by the sample launch, and what
+            // passed of them already heads the candidate regions; the scan of a list's first chunk starts behind them)
+            const uint32_t b0 = FILTER && tl.vec_begin == 0 ? TRI_SAMPLE_VECS / TRI_VB : 0u;
             // the stream's first RG groups go out before anything else
             uint32_t off = r * row_bytes + kg * 16 + b0 * blk_bytes;
             uint4 buf[RG][4];
@@ -339,7 +339,7 @@ __device__ __forceinline__ void scan_tile_pipelined(const TriTile &tl, const uin
     const uint32_t lane_off = 4 * kg * pitch_bytes + r * 4;
     constexpr uint32_t bstride = (TRI_SCAN_THREADS / 64) * TRI_VB * row_bytes;   // to the wavefront's next block
 
-    const uint32_t b0 = FILTER && tl.vec_begin == 0 ? 1u : 0u;    // (the sample launch scored the list's first block)
+    const uint32_t b0 = FILTER && tl.vec_begin == 0 ? TRI_SAMPLE_VECS / TRI_VB : 0u;    // (the sample launch scored the list's first blocks)
     uint32_t off = ((b0 + wave) * TRI_VB + r) * row_bytes + kg * 16;
     uint4 buf[SCAN_RING][4];
 #pragma unroll
@@ -409,7 +409,7 @@ __device__ __forceinline__ void scan_tile_generic(const TriTile &tl, const uint8
         SCAN_BUF_FLAGS);
     const uint32_t lane_off = 4 * kg * pitch_bytes + r * 4;
 
-    const uint32_t b0 = FILTER && tl.vec_begin == 0 ? 1u : 0u;    // (the sample launch scored the list's first block)
+    const uint32_t b0 = FILTER && tl.vec_begin == 0 ? TRI_SAMPLE_VECS / TRI_VB : 0u;    // (the sample launch scored the list's first blocks)
     for (uint32_t b = b0 + wave; b < nblocks; b += TRI_SCAN_THREADS / 64) {
         const uint32_t off = (b * TRI_VB + r) * row_bytes + kg * 16;
         const float vn = __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(nrs, (b * TRI_VB + r) * 4u, 0, 0));

@@ -683,7 +683,8 @@ __global__ __launch_bounds__(TRI_SEL_THREADS) void slot_threshold_kernel(
     uint32_t *__restrict__ thr_key, const uint64_t *__restrict__ item_score_off, float *__restrict__ cand,
     uint32_t *__restrict__ surv_count)
 {
-    static_assert(TRI_SAMPLE_VECS == TRI_VB && TRI_SAMPLE_VECS == 32, "the sample is the first block of a list");
+    static_assert(TRI_SAMPLE_VECS % TRI_VB == 0 && TRI_VB == 32, "the sample is the first blocks of a list");
+    static_assert(TRI_THRESH_ITEMS * TRI_SAMPLE_VECS + TRI_KMAX_POW2 <= 2 * SEL_CAP, "the sample keys must fit the LDS array");
     __shared__ SelShared sh;
     const TriStepHdr *hdr = (const TriStepHdr *)upload;
     if (blockIdx.x >= hdr->n_plan) return;
@@ -703,7 +704,7 @@ __global__ __launch_bounds__(TRI_SEL_THREADS) void slot_threshold_kernel(
                            (uint32_t)(item_score_off[it] / 2u), 0u};
     }
     __syncthreads();
-    // keys[s * 32 + l] = key of sample l of item s (all-ones where the list is shorter), then the running top-k
+    // keys[s * TRI_SAMPLE_VECS + l] = key of sample l of item s (all-ones where the list is shorter), then the running top-k
     const uint32_t nsample = nitems * TRI_SAMPLE_VECS, n = nsample + have;
     uint32_t valid_here = 0;
     for (uint32_t i = threadIdx.x; i < n; i += TRI_SEL_THREADS) {
@@ -724,13 +725,13 @@ __global__ __launch_bounds__(TRI_SEL_THREADS) void slot_threshold_kernel(
     uint32_t thr = 0xFFFFFFFFu;
     if (nvalid >= meta.k) thr = sel_keys_threshold(sh, keys, n, meta.k);
     if (threadIdx.x == 0) thr_key[e.slot] = thr;
-    // The sample IS the first block of every list: its scores that pass the threshold become the first
-    // candidates of their (query, list) item here, and the scan starts at the second block.  One item per
+    // The sample IS the first block(s) of every list: its scores that pass the threshold become the first
+    // candidates of their (query, list) item here, and the scan starts behind them.  One item per
     // half-wavefront; (score bits, position) pairs at the head of the item's region, their number in the
     // item's first counter (the scan counts on from there).
     // (The first TRI_THRESH_ITEMS items' keys are still in LDS -- a key gives back its score bit for bit --;
     // items beyond them, and beyond the cached descriptors, are read again.)
-    const uint32_t l = threadIdx.x & 31;
+    const uint32_t l32 = threadIdx.x & 31;
     for (uint32_t s = threadIdx.x >> 5; s < e.take; s += TRI_SEL_THREADS / 32) {
         uint32_t row, n_l, first_pair;
         if (s < ncached) {
@@ -741,13 +742,19 @@ __global__ __launch_bounds__(TRI_SEL_THREADS) void slot_threshold_kernel(
             n_l = min(glist_len[item_glist[it]], (uint32_t)TRI_SAMPLE_VECS);
             first_pair = (uint32_t)(item_score_off[it] / 2u);
         }
-        uint32_t key = 0xFFFFFFFFu;
-        if (l < n_l) key = s < nitems ? keys[s * TRI_SAMPLE_VECS + l] : sel_key(sample_scores[(size_t)row * TRI_SAMPLE_VECS + l], desc);
-        const bool pass = l < n_l && key <= thr;
-        const uint64_t m = __ballot(pass);
-        const uint32_t half = (threadIdx.x & 32) ? (uint32_t)(m >> 32) : (uint32_t)m;
-        if (pass) ((uint2 *)cand)[(size_t)first_pair + __popc(half & ((1u << l) - 1u))] = make_uint2(__float_as_uint(sel_unkey(key, desc)), l);
-        if (l == 0) surv_count[row * TRI_TILES_PER_ITEM] = (uint32_t)__popc(half);
+        uint32_t kept = 0;
+#pragma unroll
+        for (uint32_t sb = 0; sb < TRI_SAMPLE_VECS / 32; ++sb) {      // 32 samples at a time
+            const uint32_t l = sb * 32 + l32;
+            uint32_t key = 0xFFFFFFFFu;
+            if (l < n_l) key = s < nitems ? keys[s * TRI_SAMPLE_VECS + l] : sel_key(sample_scores[(size_t)row * TRI_SAMPLE_VECS + l], desc);
+            const bool pass = l < n_l && key <= thr;
+            const uint64_t m = __ballot(pass);
+            const uint32_t half = (threadIdx.x & 32) ? (uint32_t)(m >> 32) : (uint32_t)m;
+            if (pass) ((uint2 *)cand)[(size_t)first_pair + kept + __popc(half & ((1u << l32) - 1u))] = make_uint2(__float_as_uint(sel_unkey(key, desc)), l);
+            kept += (uint32_t)__popc(half);
+        }
+        if (l32 == 0) surv_count[row * TRI_TILES_PER_ITEM] = kept;
     }
 }
 

@@ -95,7 +95,7 @@ struct TriTile {
     uint32_t chunk;       // chunk number inside the list (main tiles)
 };
 
-#define TRI_SAMPLE_VECS 32     // vectors per list scored ahead of the scan to find each query's threshold
+#define TRI_SAMPLE_VECS 64     // vectors per list scored ahead of the scan to find each query's threshold
 #define TRI_THRESH_ITEMS 96    // at most this many items' samples enter one query's threshold
 
 // Order-preserving image of an fp32 score: ascending key = better (bit-flipped for inner product).
