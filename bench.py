@@ -29,7 +29,7 @@ HBM_PEAK_GBS = 8000.0   # MI355X published HBM3E bandwidth
 # HBM bytes one launch of the list-scan kernel moves at configuration 4, measured with rocprofv3 --pmc
 # FETCH_SIZE / WRITE_SIZE (each scaled by the same counter's reading for a 1 GiB device copy); the runs
 # are summarised in profiles/scan_kernel_config4.txt.  Not measurable from inside this script.
-MEASURED_TRAFFIC_BYTES = {4: 15.203e9}
+MEASURED_TRAFFIC_BYTES = {4: 14.373e9}
 # The same for one launch of the graph engine's step kernel in the default graph workload
 # (profiles/graph_step_kernel.txt).
 GRAPH_TRAFFIC_BYTES = 0.914e9
