@@ -354,7 +354,7 @@ typedef struct {
     double select_ms;        /* per-query top-k merge, result copy-out enqueue                     */
     uint64_t scan_launches;  /* list-scan kernel launches                                          */
     uint64_t scan_vector_bytes; /* bytes of inverted-list vectors those launches had to read: each
-                                   (list, query-group) tile counted once; a list's first 32 vectors
+                                   (list, query-group) tile counted once; a list's first 64 vectors
                                    are scored by the sample launch and not counted here             */
     uint64_t scan_unique_bytes; /* same, each distinct list counted once per step                  */
     uint64_t scan_items;     /* work items scanned                                                 */
