@@ -232,6 +232,41 @@ def test_serving_loop_continuous_and_static_batches():
             pool.run_stream(Q, arrival[::-1].copy(), k, metric)          # arrival times must not decrease
 
 
+def test_high_class_is_admitted_first():
+    """Two classes: with every slot taken and low-class queries waiting, a high-class query submitted later gets the
+    first slot that frees."""
+    tri, tg = _lib()
+    rng = np.random.default_rng(8)
+    n, dim = 4000, 32
+    X = rng.integers(-4, 5, size=(n, dim)).astype(np.float32)
+    G = rng.integers(0, n, size=(n, 8)).astype(np.uint32)
+    Q = rng.integers(-4, 5, size=(12, dim)).astype(np.float32)
+    seeds = rng.choice(n, size=8, replace=False).astype(np.uint32)
+    with tg.GraphPool(X, G, seeds, tri.TRI_F32, slots=2, topm=16, parents=2, max_iters=20, max_outstanding=64, groups=1) as pool:
+        low, rc = pool.submit(Q[:10], 5, tri.TRI_L2)
+        pool.step()                                                   # two low-class queries running, eight waiting
+        high, rc = pool.submit(Q[10:11], 5, tri.TRI_L2, klass=np.array([tri.TRI_CLASS_HIGH], dtype=np.uint32))
+        done_at = {}
+        for step in range(1, 2000):
+            st = pool.step()
+            pool.sync()
+            for name, t in [("high", high[0])] + [(f"low{i}", t) for i, t in enumerate(low)]:
+                if name not in done_at:
+                    status = pool.poll(np.array([t], dtype=np.uint64), 5)[5]
+                    if status[0] == tri.TRI_OK:
+                        done_at[name] = step
+            if len(done_at) == 11:
+                break
+        assert len(done_at) == 11
+        # none of the eight low-class queries that were waiting when it arrived finishes before it started, and at
+        # least six of them finish strictly after it (at most one can share its step in the other slot each time)
+        later = sum(1 for i in range(2, 10) if done_at[f"low{i}"] > done_at["high"])
+        assert later >= 6, done_at
+        want = _oracle_all(X, G, seeds, Q[10:11], 5, tri.TRI_L2, 16, 2, 20)
+        ids, dist, n_out, it, ev, _ = pool.run_all(Q[10:11], 5, tri.TRI_L2)
+        _check_exact((ids, dist, n_out, it, ev), want, 5)
+
+
 def test_argument_errors_and_empty_steps():
     tri, tg = _lib()
     X = np.arange(32, dtype=np.float32).reshape(16, 2)

@@ -499,6 +499,15 @@ def test_control_loop_moves_the_policy_inside_the_pool():
             tri.search_report_signals(pool.handle, 1.5, 0.0)
 
 
+def test_streaming_read_probe_measures_something_plausible():
+    import torch
+    tri = harness.lib()
+    buf = torch.ones(64 << 20, dtype=torch.float32, device="cuda")       # 256 MiB
+    gbs = tri.tri_stream_read_bandwidth(buf, 5)
+    _say(f"streaming read of 256 MiB: {gbs:.0f} GB/s")
+    assert 200.0 < gbs < 20000.0
+
+
 def test_static_batches_drain_before_admitting():
     """tri_policy.static_batches (the scheme continuous batching replaces, kept for comparison): no query is
     admitted while one is running; results are those of continuous batching."""

@@ -165,6 +165,18 @@ def test_slack_order_properties(tri):
     assert tri.tri_policy_slack_order(np.zeros(0, np.int64), np.zeros(0, np.uint32), now, step).shape == (0,)
 
 
+def test_streaming_read_probe_rejects_bad_arguments(tri):
+    lib = ctypes.CDLL(tri.LIB_PATH)
+    lib.tri_stream_read_bandwidth.argtypes = [ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_uint32,
+                                              ctypes.POINTER(ctypes.c_double)]
+    out = ctypes.c_double(0.0)
+    assert lib.tri_stream_read_bandwidth(None, 1 << 20, None, None, 1, ctypes.byref(out)) == tri.TRI_EINVAL
+    assert lib.tri_stream_read_bandwidth(ctypes.c_void_p(4096), 100, ctypes.c_void_p(4096), None, 1, ctypes.byref(out)) == tri.TRI_EINVAL
+    assert lib.tri_stream_read_bandwidth(ctypes.c_void_p(4096), 1 << 20, ctypes.c_void_p(4096), None, 0, ctypes.byref(out)) == tri.TRI_EINVAL
+    assert lib.tri_stream_read_bandwidth(ctypes.c_void_p(4100), 1 << 20, ctypes.c_void_p(4096), None, 1, ctypes.byref(out)) == tri.TRI_EINVAL
+    assert "aligned" in tri.tri_last_error()
+
+
 def test_graph_header_exports_layouts_and_validation(tri):
     """include/trinity_graph.h: every declared function is exported and bound, the structs have the layout the
     binding assumes, and the size query validates its arguments (no GPU needed)."""
