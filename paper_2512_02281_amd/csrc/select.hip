@@ -28,7 +28,8 @@
 
 #define SEL_BINS 2048
 #define SEL_SEGCACHE 544   // pair-segment descriptors cached in LDS (128 lists x 4 chunks, and some)
-#define SEL_CAP 4096       // composites held in LDS
+#define SEL_CAP 2816       // composites held in LDS; chosen so that a workgroup stays under 40 KB of LDS and four of
+                           // them share a compute unit (with 4096 three did, and the three selection kernels ran slower)
 #define SEL_SMALL 1024     // composites in the second array (which shares its storage with the histogram)
 #define SEL_RANK_MAX 256   // sorted by rank counting up to here (one element per thread)
 #define SEL_SAMPLE 1024    // target size of the key sample

@@ -96,7 +96,7 @@ struct TriTile {
 };
 
 #define TRI_SAMPLE_VECS 64     // vectors per list scored ahead of the scan to find each query's threshold
-#define TRI_THRESH_ITEMS 96    // at most this many items' samples enter one query's threshold
+#define TRI_THRESH_ITEMS 72    // at most this many items' samples enter one query's threshold
 
 // Order-preserving image of an fp32 score: ascending key = better (bit-flipped for inner product).
 __device__ __forceinline__ uint32_t tri_score_key(float f, uint32_t descending)
