@@ -419,6 +419,49 @@ def test_recorded_step_replays_match_kernel_by_kernel_launches():
     assert float(scratch[0]) > 0
 
 
+@pytest.mark.parametrize("seed", [11, 12, 13, 14])
+def test_random_configurations_against_the_oracle(seed):
+    """Seeded random shapes nobody picked by hand: dimension (any, not only multiples of the row padding), base size,
+    number and balance of lists, slots, lists per step, items per step, storage type, per-query k / nprobe / metric /
+    class, arrivals in chunks -- each compared with the oracle query by query."""
+    tri = harness.lib()
+    rng = np.random.default_rng(seed)
+    for case in range(3):
+        dim = int(rng.choice([3, 17, 40, 64, 100, 128, 200, 257, 384, 500]))
+        f16 = bool(rng.integers(0, 2))
+        n = int(rng.integers(500, 12_000))
+        nlist = int(rng.integers(2, 97))
+        nq = int(rng.integers(1, 120))
+        spread = float(rng.choice([0.3, 1.0, 3.0]))                  # tight clusters ... one blob (very uneven lists)
+        centres = rng.standard_normal((nlist, dim)).astype(np.float32)
+        weights = rng.dirichlet(np.full(nlist, 0.5))                 # unbalanced list sizes, some nearly empty
+        base = (centres[rng.choice(nlist, size=n, p=weights)] + spread * rng.standard_normal((n, dim))).astype(np.float32)
+        queries = (centres[rng.integers(0, nlist, size=nq)] + spread * rng.standard_normal((nq, dim))).astype(np.float32)
+        if f16:
+            scale = 1.0 / np.sqrt(dim)
+            base, queries = (base * scale).astype(np.float16), (queries * scale).astype(np.float16)
+        k = rng.integers(1, 130, size=nq).astype(np.uint32)
+        nprobe = rng.integers(1, nlist + 1, size=nq).astype(np.uint32)
+        metric = rng.integers(0, 2, size=nq).astype(np.uint32)
+        klass = rng.integers(0, 2, size=nq).astype(np.uint32)
+        slots = int(rng.integers(1, 70))
+        p = int(rng.choice([0, 1, 2, 5]))
+        items = int(rng.integers(1, 400)) if p else slots * nlist
+        chunks = [int(c) for c in rng.integers(1, 30, size=4)]
+        _say(f"random case {seed}.{case}: dim {dim} {'f16' if f16 else 'f32'} n {n} nlist {nlist} nq {nq} slots {slots} "
+             f"p {p} W {items} spread {spread}")
+        with harness.default_pool(tri, slots=slots, items_per_step=items, lists_per_query_step=p, kmax=129, nprobe_max=nlist,
+                                  max_dim=dim, max_nlist=nlist, max_total_lists=nlist, max_outstanding=max(256, slots),
+                                  score_capacity=32 << 20) as pool:
+            idx = pool.build_index(base, dim, nlist, tri.TRI_F16 if f16 else tri.TRI_F32, int(rng.integers(0, 2)), 3,
+                                   centroids=centres)
+            oidx = harness.oracle_index(tri, idx, base)
+            q = tri.make_queries(idx, queries, k, nprobe, metric, klass)
+            ids, dist, n_out, probes, stats = harness.run_all(tri, pool, q, submit_chunks=chunks)
+            rep = harness.compare_with_oracle(oidx, base, queries, k, nprobe, metric, ids, dist, n_out, probes)
+            _say(f"  {len(stats)} steps, parity {rep}")
+
+
 def test_more_probed_lists_than_cached_segments():
     """nprobe far beyond what the merge kernel caches of candidate segments (200 lists x 4 chunk
     segments in one step), small lists, and a k that keeps nearly everything."""
