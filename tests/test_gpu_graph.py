@@ -123,6 +123,41 @@ def test_real_valued_data_valid_results_and_recall():
     assert abs(r_gpu - r_orc) <= 0.02 and same >= 0.9 * nq
 
 
+@pytest.mark.parametrize("seed", [21, 22, 23])
+def test_random_configurations_against_the_oracle(seed):
+    """Seeded random shapes: database size, dimension (any), degree, topM, parents, entry points, extend budget, slots and
+    groups, storage type, per-query k and metric, random neighbour lists with padding and self-loops -- on integer-valued
+    data, so everything must equal the oracle exactly."""
+    tri, tg = _lib()
+    rng = np.random.default_rng(seed)
+    for case in range(4):
+        n = int(rng.integers(1, 5000))
+        dim = int(rng.choice([1, 5, 33, 64, 100, 128, 300, 640]))
+        degree = int(rng.choice([1, 2, 7, 16, 32, 64]))
+        p = int(rng.integers(1, max(2, 256 // degree + 1)))
+        M = int(rng.integers(1, 257))
+        iters = int(rng.choice([0, 1, 5, 30, 30, 64]))
+        n_seeds = int(rng.integers(1, 257))
+        f16 = bool(rng.integers(0, 2))
+        dt = np.float16 if f16 else np.float32
+        X = rng.integers(-6, 7, size=(n, dim)).astype(dt)
+        G = rng.integers(0, n, size=(n, degree)).astype(np.uint32)
+        G[rng.random(G.shape) < 0.05] = tg.TRI_GRAPH_PAD
+        seeds = rng.integers(0, n + 3, size=n_seeds).astype(np.uint32)          # duplicates and a few invalid ones
+        nq = int(rng.integers(1, 90))
+        Q = rng.integers(-6, 7, size=(nq, dim)).astype(dt)
+        k = rng.integers(1, M + 1, size=nq).astype(np.uint32)
+        metric = rng.integers(0, 2, size=nq).astype(np.uint32)
+        slots, groups = int(rng.integers(1, 40)), int(rng.integers(1, 5))
+        _say(f"random case {seed}.{case}: n {n} dim {dim} {'f16' if f16 else 'f32'} degree {degree} p {p} topM {M} extends <= {iters} "
+             f"entry points {n_seeds} queries {nq} slots {slots} groups {groups}")
+        want = _oracle_all(X, G, seeds, Q, k, metric, M, p, iters)
+        with tg.GraphPool(X, G, seeds, tri.TRI_F16 if f16 else tri.TRI_F32, slots=slots, topm=M, parents=p, max_iters=iters,
+                          max_outstanding=256, groups=groups) as pool:
+            got = pool.run_all(Q, k, metric)
+            _check_exact(got[:5], want, k)
+
+
 def test_largest_shapes_and_degenerate_graphs():
     """The limits of the implementation in one pool -- topM 256, parents * degree 256, 256 entry points, rows of
     4096 bytes, k = topM, a database whose size is no multiple of 32 -- and degenerate graphs: degree 1 (a ring),
