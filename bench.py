@@ -15,6 +15,8 @@ open-loop runs at fractions of it with p50 / p99 latency per class.
 from __future__ import annotations
 
 import argparse
+import contextlib
+import ctypes
 import json
 import os
 import sys
@@ -37,6 +39,19 @@ GRAPH_TRAFFIC_BYTES = 0.914e9
 
 def log(msg):
     print(f"[bench] {msg}", file=sys.stderr, flush=True)
+
+
+@contextlib.contextmanager
+def one_omp_thread():
+    """Hold the OpenMP runtime the CPU oracle runs on to one thread (the oracle itself is not touched)."""
+    omp = ctypes.CDLL("libgomp.so.1")
+    omp.omp_get_max_threads.restype = ctypes.c_int
+    before = omp.omp_get_max_threads()
+    omp.omp_set_num_threads(1)
+    try:
+        yield
+    finally:
+        omp.omp_set_num_threads(before)
 
 
 def main():
@@ -263,6 +278,16 @@ def main():
         tc = time.perf_counter() - tc0
         cpu = {"value": round(sel.size / tc, 3), "unit": "queries/s", "cores": out["threads"], "kind": "oracle",
                "sample": f"{sel.size} queries of the same batch (every {max(1, Q // n_cpu)}-th), {tc:.1f} s of wall time"}
+        # the same oracle held to one thread, on a smaller sample sized from the rate just measured
+        n_one = int(min(sel.size, max(8, 6.0 * sel.size / tc / max(1, out["threads"]))))
+        one = sel[:: max(1, sel.size // n_one)][:n_one]
+        with one_omp_thread():
+            t1 = time.perf_counter()
+            out1 = oracle.search_batch(oidx, queries_t.cpu().numpy()[one], k[one], nprobe[one], metric_arr[one])
+            t1 = time.perf_counter() - t1
+        if out1["threads"] == 1:
+            cpu["one_core"] = {"value": round(one.size / t1, 3), "unit": "queries/s",
+                               "sample": f"{one.size} of those queries, {t1:.1f} s"}
         log(f"cpu oracle: {cpu}")
 
     result = {

@@ -20,20 +20,7 @@
 #include <vector>
 
 namespace {
-
 thread_local std::string g_err;
-
-int fail(int code, const char *fmt, ...)
-{
-    char buf[512];
-    va_list ap;
-    va_start(ap, fmt);
-    vsnprintf(buf, sizeof buf, fmt, ap);
-    va_end(ap);
-    g_err = buf;
-    return code;
-}
-
 }  // namespace
 
 int tri_fail(int code, const char *fmt, ...)
@@ -52,7 +39,7 @@ namespace {
 #define HIP_TRY(expr)                                                                          \
     do {                                                                                       \
         hipError_t e_ = (expr);                                                                \
-        if (e_ != hipSuccess) return fail(TRI_EHIP, "%s -> %s", #expr, hipGetErrorString(e_)); \
+        if (e_ != hipSuccess) return tri_fail(TRI_EHIP, "%s -> %s", #expr, hipGetErrorString(e_)); \
     } while (0)
 
 constexpr uint32_t RING = 4;          // steps that may be in flight before search_step waits
@@ -256,29 +243,29 @@ size_t carve(const tri_pool_cfg &c, uint32_t max_row_bytes, uint32_t coarse_rows
 int derive(const tri_pool_cfg *c, uint32_t *max_row_bytes, uint32_t *coarse_rows, uint32_t *coarse_ldc,
            uint64_t *score_capacity, size_t *upload_bytes)
 {
-    if (!c) return fail(TRI_EINVAL, "cfg is NULL");
-    if (c->slots == 0 || c->slots > (1u << 20)) return fail(TRI_EINVAL, "slots must be 1..2^20");
-    if (c->items_per_step == 0) return fail(TRI_EINVAL, "items_per_step must be > 0");
-    if (c->kmax == 0 || c->kmax > TRI_KMAX_LIMIT) return fail(TRI_EINVAL, "kmax must be 1..%u", TRI_KMAX_LIMIT);
+    if (!c) return tri_fail(TRI_EINVAL, "cfg is NULL");
+    if (c->slots == 0 || c->slots > (1u << 20)) return tri_fail(TRI_EINVAL, "slots must be 1..2^20");
+    if (c->items_per_step == 0) return tri_fail(TRI_EINVAL, "items_per_step must be > 0");
+    if (c->kmax == 0 || c->kmax > TRI_KMAX_LIMIT) return tri_fail(TRI_EINVAL, "kmax must be 1..%u", TRI_KMAX_LIMIT);
     if (c->nprobe_max == 0 || c->nprobe_max > TRI_NPROBE_LIMIT)
-        return fail(TRI_EINVAL, "nprobe_max must be 1..%u", TRI_NPROBE_LIMIT);
-    if (c->max_indexes == 0 || c->max_indexes > 256) return fail(TRI_EINVAL, "max_indexes must be 1..256");
+        return tri_fail(TRI_EINVAL, "nprobe_max must be 1..%u", TRI_NPROBE_LIMIT);
+    if (c->max_indexes == 0 || c->max_indexes > 256) return tri_fail(TRI_EINVAL, "max_indexes must be 1..256");
     if (c->max_nlist == 0 || c->max_total_lists < c->max_nlist)
-        return fail(TRI_EINVAL, "need 0 < max_nlist <= max_total_lists");
-    if (c->max_dim == 0) return fail(TRI_EINVAL, "max_dim must be > 0");
-    if (c->max_outstanding < c->slots) return fail(TRI_EINVAL, "max_outstanding must be >= slots");
+        return tri_fail(TRI_EINVAL, "need 0 < max_nlist <= max_total_lists");
+    if (c->max_dim == 0) return tri_fail(TRI_EINVAL, "max_dim must be > 0");
+    if (c->max_outstanding < c->slots) return tri_fail(TRI_EINVAL, "max_outstanding must be >= slots");
     const uint32_t rb = round_up(c->max_dim * 4u, 128u);   // fp32 rows are the widest
     const uint32_t rb16 = round_up(c->max_dim * 2u, 128u);
-    if (rb16 > TRI_MAX_ROW_BYTES) return fail(TRI_EINVAL, "max_dim too large: padded fp16 row exceeds %u bytes", TRI_MAX_ROW_BYTES);
+    if (rb16 > TRI_MAX_ROW_BYTES) return tri_fail(TRI_EINVAL, "max_dim too large: padded fp16 row exceeds %u bytes", TRI_MAX_ROW_BYTES);
     *max_row_bytes = rb > TRI_MAX_ROW_BYTES ? TRI_MAX_ROW_BYTES : rb;
     if ((uint64_t)c->slots * *max_row_bytes >= (1ull << 31))
-        return fail(TRI_EINVAL, "slots * padded row bytes must stay below 2^31");
+        return tri_fail(TRI_EINVAL, "slots * padded row bytes must stay below 2^31");
     *coarse_rows = c->coarse_rows ? c->coarse_rows : 1024u;
     if (*coarse_rows > c->slots) *coarse_rows = c->slots;
     *coarse_ldc = round_up(c->max_nlist, 32u);
     *score_capacity = c->score_capacity ? c->score_capacity : (uint64_t)c->items_per_step * 2048u;
     if (*score_capacity > (1ull << 32))      // candidate pairs are addressed with 32-bit pair numbers
-        return fail(TRI_EINVAL, "score_capacity must not exceed 2^32 words");
+        return tri_fail(TRI_EINVAL, "score_capacity must not exceed 2^32 words");
     *upload_bytes = sizeof(TriStepHdr) + round_up_sz((size_t)c->slots * sizeof(TriNewDesc), 256) +
                     round_up_sz((size_t)c->slots * sizeof(TriPlanEntry), 256) + (size_t)c->slots * *max_row_bytes;
     return TRI_OK;
@@ -299,7 +286,7 @@ int reap(tri_pool *P, bool block, uint32_t *finished)
         } else {
             hipError_t q = hipEventQuery(R->done);
             if (q == hipErrorNotReady) break;
-            if (q != hipSuccess) return fail(TRI_EHIP, "hipEventQuery -> %s", hipGetErrorString(q));
+            if (q != hipSuccess) return tri_fail(TRI_EHIP, "hipEventQuery -> %s", hipGetErrorString(q));
         }
         if (R->had_scan) {
             // mean step duration: completion to completion while the GPU is kept busy, else enqueue to completion
@@ -419,13 +406,13 @@ bool ticket_lookup(tri_pool *P, tri_ticket t, uint32_t *idx)
 
 int validate_query(tri_pool *P, const tri_query *q)
 {
-    if (!q->index || q->index->pool != P) return fail(TRI_EINVAL, "query.index is not attached to this pool");
-    if (!q->vec) return fail(TRI_EINVAL, "query.vec is NULL");
-    if (q->k == 0 || q->k > P->cfg.kmax) return fail(TRI_EINVAL, "k=%u outside 1..%u", q->k, P->cfg.kmax);
+    if (!q->index || q->index->pool != P) return tri_fail(TRI_EINVAL, "query.index is not attached to this pool");
+    if (!q->vec) return tri_fail(TRI_EINVAL, "query.vec is NULL");
+    if (q->k == 0 || q->k > P->cfg.kmax) return tri_fail(TRI_EINVAL, "k=%u outside 1..%u", q->k, P->cfg.kmax);
     if (q->nprobe == 0 || q->nprobe > P->cfg.nprobe_max || q->nprobe > q->index->p.nlist)
-        return fail(TRI_EINVAL, "nprobe=%u outside 1..min(%u, nlist=%u)", q->nprobe, P->cfg.nprobe_max, q->index->p.nlist);
-    if (q->metric != TRI_L2 && q->metric != TRI_IP) return fail(TRI_EINVAL, "metric must be TRI_L2 or TRI_IP");
-    if (q->klass != TRI_CLASS_HIGH && q->klass != TRI_CLASS_LOW) return fail(TRI_EINVAL, "klass must be TRI_CLASS_HIGH or TRI_CLASS_LOW");
+        return tri_fail(TRI_EINVAL, "nprobe=%u outside 1..min(%u, nlist=%u)", q->nprobe, P->cfg.nprobe_max, q->index->p.nlist);
+    if (q->metric != TRI_L2 && q->metric != TRI_IP) return tri_fail(TRI_EINVAL, "metric must be TRI_L2 or TRI_IP");
+    if (q->klass != TRI_CLASS_HIGH && q->klass != TRI_CLASS_LOW) return tri_fail(TRI_EINVAL, "klass must be TRI_CLASS_HIGH or TRI_CLASS_LOW");
     return TRI_OK;
 }
 
@@ -460,7 +447,7 @@ extern "C" int tri_pool_workspace_bytes(const tri_pool_cfg *cfg, size_t *dev_byt
     size_t up;
     int rc = derive(cfg, &mrb, &cr, &ldc, &sc, &up);
     if (rc) return rc;
-    if (!dev_bytes) return fail(TRI_EINVAL, "dev_bytes is NULL");
+    if (!dev_bytes) return tri_fail(TRI_EINVAL, "dev_bytes is NULL");
     *dev_bytes = carve(*cfg, mrb, cr, ldc, sc, up, nullptr, nullptr);
     return TRI_OK;
 }
@@ -472,21 +459,21 @@ extern "C" int tri_pool_create(const tri_pool_cfg *cfg, void *dev_ws, size_t dev
     size_t up;
     int rc = derive(cfg, &mrb, &cr, &ldc, &sc, &up);
     if (rc) return rc;
-    if (!dev_ws || !out) return fail(TRI_EINVAL, "dev_ws / out is NULL");
+    if (!dev_ws || !out) return tri_fail(TRI_EINVAL, "dev_ws / out is NULL");
     if ((cfg->flags & TRI_FLAG_GRAPH) && !cfg->hip_stream)
-        return fail(TRI_EINVAL, "TRI_FLAG_GRAPH needs a stream of the pool's own: a step cannot be recorded on the default stream");
-    if ((uintptr_t)dev_ws % 256) return fail(TRI_EINVAL, "dev_ws must be 256-byte aligned");
+        return tri_fail(TRI_EINVAL, "TRI_FLAG_GRAPH needs a stream of the pool's own: a step cannot be recorded on the default stream");
+    if ((uintptr_t)dev_ws % 256) return tri_fail(TRI_EINVAL, "dev_ws must be 256-byte aligned");
     const size_t need = carve(*cfg, mrb, cr, ldc, sc, up, nullptr, nullptr);
-    if (dev_ws_bytes < need) return fail(TRI_ENOMEM, "dev_ws has %zu bytes, %zu needed", dev_ws_bytes, need);
+    if (dev_ws_bytes < need) return tri_fail(TRI_ENOMEM, "dev_ws has %zu bytes, %zu needed", dev_ws_bytes, need);
     int ndev = 0;
-    if (hipGetDeviceCount(&ndev) != hipSuccess || ndev == 0) return fail(TRI_EHIP, "no HIP device");
+    if (hipGetDeviceCount(&ndev) != hipSuccess || ndev == 0) return tri_fail(TRI_EHIP, "no HIP device");
     tri_pool *P = new (std::nothrow) tri_pool();
-    if (!P) return fail(TRI_ENOMEM, "out of host memory");
+    if (!P) return tri_fail(TRI_ENOMEM, "out of host memory");
     P->cfg = *cfg;
     hipError_t e = hipGetDevice(&P->device);
     hipDeviceProp_t prop;
     if (e == hipSuccess) e = hipGetDeviceProperties(&prop, P->device);
-    if (e != hipSuccess) { delete P; return fail(TRI_EHIP, "device query -> %s", hipGetErrorString(e)); }
+    if (e != hipSuccess) { delete P; return tri_fail(TRI_EHIP, "device query -> %s", hipGetErrorString(e)); }
     P->stream = (hipStream_t)cfg->hip_stream;
     P->max_row_bytes = mrb; P->coarse_rows = cr; P->coarse_ldc = ldc; P->score_capacity = sc; P->upload_bytes = up;
     carve(*cfg, mrb, cr, ldc, sc, up, (uint8_t *)dev_ws, &P->ws);
@@ -501,20 +488,20 @@ extern "C" int tri_pool_create(const tri_pool_cfg *cfg, void *dev_ws, size_t dev
     P->down_bytes = blk + prb + 256;
     const size_t per = round_up_sz(up, 256) + P->down_bytes;
     e = hipHostMalloc((void **)&P->pinned, per * RING, hipHostMallocDefault);
-    if (e != hipSuccess) { delete P; return fail(TRI_EHIP, "hipHostMalloc(%zu) -> %s", per * RING, hipGetErrorString(e)); }
+    if (e != hipSuccess) { delete P; return tri_fail(TRI_EHIP, "hipHostMalloc(%zu) -> %s", per * RING, hipGetErrorString(e)); }
     e = hipHostMalloc((void **)&P->qstore, (size_t)cfg->max_outstanding * mrb, hipHostMallocDefault);
     if (e == hipSuccess) e = hipHostGetDevicePointer((void **)&P->qstore_dev, P->qstore, 0);
-    if (e != hipSuccess) { tri_pool_destroy(P); return fail(TRI_EHIP, "hipHostMalloc(query store) -> %s", hipGetErrorString(e)); }
+    if (e != hipSuccess) { tri_pool_destroy(P); return tri_fail(TRI_EHIP, "hipHostMalloc(query store) -> %s", hipGetErrorString(e)); }
     for (uint32_t i = 0; i < RING; ++i) {
         StepRec &R = P->ring[i];
         R.up_host = P->pinned + i * per;
         R.down_host = R.up_host + round_up_sz(up, 256);
         e = hipHostGetDevicePointer((void **)&R.down_dev, R.down_host, 0);
         if (e == hipSuccess) e = hipHostGetDevicePointer((void **)&R.up_dev, R.up_host, 0);
-        if (e != hipSuccess) { tri_pool_destroy(P); return fail(TRI_EHIP, "hipHostGetDevicePointer -> %s", hipGetErrorString(e)); }
+        if (e != hipSuccess) { tri_pool_destroy(P); return tri_fail(TRI_EHIP, "hipHostGetDevicePointer -> %s", hipGetErrorString(e)); }
         e = hipEventCreateWithFlags(&R.done, hipEventDisableTiming);
         for (uint32_t j = 0; j < N_EV && e == hipSuccess; ++j) e = hipEventCreateWithFlags(&R.ev[j], hipEventDisableSystemFence);   // (timing only: nothing on the host reads what the kernels between them wrote)
-        if (e != hipSuccess) { tri_pool_destroy(P); return fail(TRI_EHIP, "hipEventCreate -> %s", hipGetErrorString(e)); }
+        if (e != hipSuccess) { tri_pool_destroy(P); return tri_fail(TRI_EHIP, "hipEventCreate -> %s", hipGetErrorString(e)); }
     }
     try {
         P->tickets.resize(cfg->max_outstanding);
@@ -531,7 +518,7 @@ extern "C" int tri_pool_create(const tri_pool_cfg *cfg, void *dev_ws, size_t dev
         P->newq.reserve(S);
     } catch (const std::bad_alloc &) {
         tri_pool_destroy(P);
-        return fail(TRI_ENOMEM, "out of host memory");
+        return tri_fail(TRI_ENOMEM, "out of host memory");
     }
     *out = P;
     return TRI_OK;
@@ -539,9 +526,9 @@ extern "C" int tri_pool_create(const tri_pool_cfg *cfg, void *dev_ws, size_t dev
 
 extern "C" int tri_pool_destroy(tri_pool *P)
 {
-    if (!P) return fail(TRI_EINVAL, "pool is NULL");
+    if (!P) return tri_fail(TRI_EINVAL, "pool is NULL");
     for (tri_index *ix : P->indexes)
-        if (ix) return fail(TRI_EINVAL, "destroy the pool's indexes first");
+        if (ix) return tri_fail(TRI_EINVAL, "destroy the pool's indexes first");
     drop_graphs(P);
     for (uint32_t i = 0; i < RING; ++i) {
         if (P->ring[i].done) (void)hipEventDestroy(P->ring[i].done);
@@ -557,13 +544,13 @@ extern "C" int tri_pool_destroy(tri_pool *P)
 // ================================================================================== index
 extern "C" int ivf_build_bytes(const ivf_params *p, uint64_t n, size_t *dev_bytes)
 {
-    if (!p || !dev_bytes) return fail(TRI_EINVAL, "NULL argument");
-    if (p->dtype != TRI_F32 && p->dtype != TRI_F16) return fail(TRI_EINVAL, "dtype must be TRI_F32 or TRI_F16");
-    if (p->dim == 0 || p->nlist == 0 || n == 0) return fail(TRI_EINVAL, "dim, nlist and n must be > 0");
-    if (n >= (1ull << 32)) return fail(TRI_EINVAL, "n must be < 2^32");
-    if (p->nlist > n) return fail(TRI_EINVAL, "nlist > n");
+    if (!p || !dev_bytes) return tri_fail(TRI_EINVAL, "NULL argument");
+    if (p->dtype != TRI_F32 && p->dtype != TRI_F16) return tri_fail(TRI_EINVAL, "dtype must be TRI_F32 or TRI_F16");
+    if (p->dim == 0 || p->nlist == 0 || n == 0) return tri_fail(TRI_EINVAL, "dim, nlist and n must be > 0");
+    if (n >= (1ull << 32)) return tri_fail(TRI_EINVAL, "n must be < 2^32");
+    if (p->nlist > n) return tri_fail(TRI_EINVAL, "nlist > n");
     const uint32_t dpad = dpad_of(p->dim, p->dtype), rb = dpad * esize(p->dtype);
-    if (rb > TRI_MAX_ROW_BYTES) return fail(TRI_EINVAL, "padded row of %u bytes exceeds %u", rb, TRI_MAX_ROW_BYTES);
+    if (rb > TRI_MAX_ROW_BYTES) return tri_fail(TRI_EINVAL, "padded row of %u bytes exceeds %u", rb, TRI_MAX_ROW_BYTES);
     size_t o = 0;
     o += round_up_sz((size_t)n * rb, 256);                 // vectors
     o += round_up_sz(((size_t)n + TRI_VB) * 4, 256);       // |x|^2 (+ one block of slack for tail reads)
@@ -621,23 +608,23 @@ int assign_all(hipStream_t s, int dtype, uint32_t dim, uint32_t dpad, uint32_t r
 extern "C" int ivf_build(tri_pool *P, const ivf_params *p, const void *base, uint64_t n, const float *centroids,
                          void *dev_mem, size_t dev_mem_bytes, tri_index **out)
 {
-    if (!P || !p || !base || !dev_mem || !out) return fail(TRI_EINVAL, "NULL argument");
+    if (!P || !p || !base || !dev_mem || !out) return tri_fail(TRI_EINVAL, "NULL argument");
     size_t need = 0;
     int rc = ivf_build_bytes(p, n, &need);
     if (rc) return rc;
-    if (p->build_metric != TRI_L2 && p->build_metric != TRI_IP) return fail(TRI_EINVAL, "build_metric must be TRI_L2 or TRI_IP");
-    if ((uintptr_t)dev_mem % 256) return fail(TRI_EINVAL, "dev_mem must be 256-byte aligned");
-    if (dev_mem_bytes < need) return fail(TRI_ENOMEM, "dev_mem has %zu bytes, %zu needed", dev_mem_bytes, need);
+    if (p->build_metric != TRI_L2 && p->build_metric != TRI_IP) return tri_fail(TRI_EINVAL, "build_metric must be TRI_L2 or TRI_IP");
+    if ((uintptr_t)dev_mem % 256) return tri_fail(TRI_EINVAL, "dev_mem must be 256-byte aligned");
+    if (dev_mem_bytes < need) return tri_fail(TRI_ENOMEM, "dev_mem has %zu bytes, %zu needed", dev_mem_bytes, need);
     std::lock_guard<std::mutex> lk(P->mu);
-    if (p->dim > P->cfg.max_dim) return fail(TRI_EINVAL, "dim %u > pool max_dim %u", p->dim, P->cfg.max_dim);
-    if (p->nlist > P->cfg.max_nlist) return fail(TRI_EINVAL, "nlist %u > pool max_nlist %u", p->nlist, P->cfg.max_nlist);
+    if (p->dim > P->cfg.max_dim) return tri_fail(TRI_EINVAL, "dim %u > pool max_dim %u", p->dim, P->cfg.max_dim);
+    if (p->nlist > P->cfg.max_nlist) return tri_fail(TRI_EINVAL, "nlist %u > pool max_nlist %u", p->nlist, P->cfg.max_nlist);
     if ((uint64_t)P->total_lists + p->nlist > P->cfg.max_total_lists)
-        return fail(TRI_ENOMEM, "pool list table full (%u + %u > %u)", P->total_lists, p->nlist, P->cfg.max_total_lists);
+        return tri_fail(TRI_ENOMEM, "pool list table full (%u + %u > %u)", P->total_lists, p->nlist, P->cfg.max_total_lists);
     if (P->n_running || !P->pending[0].empty() || !P->pending[1].empty())
-        return fail(TRI_EINVAL, "ivf_build while queries are queued or running");
+        return tri_fail(TRI_EINVAL, "ivf_build while queries are queued or running");
     uint32_t id = 0;
     while (id < P->cfg.max_indexes && P->indexes[id]) ++id;
-    if (id == P->cfg.max_indexes) return fail(TRI_ENOMEM, "pool already holds max_indexes=%u indexes", P->cfg.max_indexes);
+    if (id == P->cfg.max_indexes) return tri_fail(TRI_ENOMEM, "pool already holds max_indexes=%u indexes", P->cfg.max_indexes);
     rc = reap(P, true, nullptr);
     if (rc) return rc;
     HIP_TRY(hipSetDevice(P->device));
@@ -647,7 +634,7 @@ extern "C" int ivf_build(tri_pool *P, const ivf_params *p, const void *base, uin
     const int dtype = (int)p->dtype, metric = (int)p->build_metric;
     const uint32_t es = esize(p->dtype), dim = p->dim, nlist = p->nlist;
     const uint32_t dpad = dpad_of(dim, p->dtype), rb = dpad * es;
-    if (rb > P->max_row_bytes) return fail(TRI_EINVAL, "padded row %u bytes > pool row %u bytes", rb, P->max_row_bytes);
+    if (rb > P->max_row_bytes) return tri_fail(TRI_EINVAL, "padded row %u bytes > pool row %u bytes", rb, P->max_row_bytes);
 
     // carve dev_mem
     uint8_t *m = (uint8_t *)dev_mem;
@@ -753,16 +740,16 @@ extern "C" int ivf_build(tri_pool *P, const ivf_params *p, const void *base, uin
     // ---- attach
     std::vector<uint32_t> h_off((size_t)nlist + 1);
     HIP_TRY(hipMemcpy(h_off.data(), loff, h_off.size() * 4, hipMemcpyDeviceToHost));
-    if (h_off[nlist] != n) return fail(TRI_EHIP, "partition produced %u rows, expected %llu", h_off[nlist], (unsigned long long)n);
+    if (h_off[nlist] != n) return tri_fail(TRI_EHIP, "partition produced %u rows, expected %llu", h_off[nlist], (unsigned long long)n);
     uint32_t maxlen = 0;
     std::vector<uint32_t> h_len(nlist), h_idx(nlist, id);
     for (uint32_t l = 0; l < nlist; ++l) { h_len[l] = h_off[l + 1] - h_off[l]; maxlen = std::max(maxlen, h_len[l]); }
     if ((uint64_t)maxlen * rb >= (1ull << 31))
-        return fail(TRI_EINVAL, "longest list (%u vectors of %u bytes) exceeds 2^31 bytes", maxlen, rb);
+        return tri_fail(TRI_EINVAL, "longest list (%u vectors of %u bytes) exceeds 2^31 bytes", maxlen, rb);
     if (2ull * round_up(maxlen, TRI_VB) > P->score_capacity)
-        return fail(TRI_ENOMEM, "longest list (%u) exceeds the pool's score capacity", maxlen);
+        return tri_fail(TRI_ENOMEM, "longest list (%u) exceeds the pool's score capacity", maxlen);
     tri_index *ix = new (std::nothrow) tri_index();
-    if (!ix) return fail(TRI_ENOMEM, "out of host memory");
+    if (!ix) return tri_fail(TRI_ENOMEM, "out of host memory");
     ix->pool = P; ix->id = id; ix->p = *p; ix->n = n; ix->dpad = dpad; ix->row_bytes = rb;
     ix->list_base = P->total_lists; ix->max_list_len = maxlen; ix->ids_dev = ids; ix->list_off_dev = loff;
     ix->dev = TriIndexDev{vecs, vnorm, ids, loff, cent, cnorm, dim, dpad, nlist, p->dtype, rb, ix->list_base, maxlen, 0, n};
@@ -770,7 +757,7 @@ extern "C" int ivf_build(tri_pool *P, const ivf_params *p, const void *base, uin
     if (e == hipSuccess) e = hipMemcpy(P->ws.glist_len + ix->list_base, h_len.data(), (size_t)nlist * 4, hipMemcpyHostToDevice);
     if (e == hipSuccess) e = hipMemcpy(P->ws.glist_voff + ix->list_base, h_off.data(), (size_t)nlist * 4, hipMemcpyHostToDevice);
     if (e == hipSuccess) e = hipMemcpy(P->ws.glist_index + ix->list_base, h_idx.data(), (size_t)nlist * 4, hipMemcpyHostToDevice);
-    if (e != hipSuccess) { delete ix; return fail(TRI_EHIP, "attach copy -> %s", hipGetErrorString(e)); }
+    if (e != hipSuccess) { delete ix; return tri_fail(TRI_EHIP, "attach copy -> %s", hipGetErrorString(e)); }
     ix->list_len = h_len;
     P->indexes[id] = ix;
     rc = upload_scan_order(P);
@@ -785,7 +772,7 @@ extern "C" int ivf_build(tri_pool *P, const ivf_params *p, const void *base, uin
 
 extern "C" int ivf_export(const tri_index *ix, float *centroids, uint64_t *list_off, int64_t *list_ids)
 {
-    if (!ix) return fail(TRI_EINVAL, "index is NULL");
+    if (!ix) return tri_fail(TRI_EINVAL, "index is NULL");
     HIP_TRY(hipSetDevice(ix->pool->device));
     HIP_TRY(hipStreamSynchronize(ix->pool->stream));
     const uint32_t nlist = ix->p.nlist, dim = ix->p.dim;
@@ -814,7 +801,7 @@ extern "C" int ivf_export(const tri_index *ix, float *centroids, uint64_t *list_
 extern "C" int ivf_info(const tri_index *ix, uint64_t *n, uint32_t *dim, uint32_t *nlist, uint32_t *dtype,
                         uint32_t *max_list_len)
 {
-    if (!ix) return fail(TRI_EINVAL, "index is NULL");
+    if (!ix) return tri_fail(TRI_EINVAL, "index is NULL");
     if (n) *n = ix->n;
     if (dim) *dim = ix->p.dim;
     if (nlist) *nlist = ix->p.nlist;
@@ -825,11 +812,11 @@ extern "C" int ivf_info(const tri_index *ix, uint64_t *n, uint32_t *dim, uint32_
 
 extern "C" int ivf_destroy(tri_index *ix)
 {
-    if (!ix) return fail(TRI_EINVAL, "index is NULL");
+    if (!ix) return tri_fail(TRI_EINVAL, "index is NULL");
     tri_pool *P = ix->pool;
     std::lock_guard<std::mutex> lk(P->mu);
     if (P->n_running || !P->pending[0].empty() || !P->pending[1].empty())
-        return fail(TRI_EINVAL, "ivf_destroy while queries are queued or running");
+        return tri_fail(TRI_EINVAL, "ivf_destroy while queries are queued or running");
     int rc = reap(P, true, nullptr);
     if (rc) return rc;
     HIP_TRY(hipStreamSynchronize(P->stream));
@@ -852,7 +839,7 @@ extern "C" int ivf_destroy(tri_index *ix)
 extern "C" int search_submit_batch(tri_pool *P, const tri_query *q, uint32_t n, tri_ticket *out, uint32_t *n_done)
 {
     if (n_done) *n_done = 0;
-    if (!P || (!q && n) || (!out && n)) return fail(TRI_EINVAL, "NULL argument");
+    if (!P || (!q && n) || (!out && n)) return tri_fail(TRI_EINVAL, "NULL argument");
     std::lock_guard<std::mutex> lk(P->mu);
     for (uint32_t i = 0; i < n; ++i) {
         int rc = validate_query(P, &q[i]);
@@ -860,7 +847,7 @@ extern "C" int search_submit_batch(tri_pool *P, const tri_query *q, uint32_t n, 
     }
     for (uint32_t i = 0; i < n; ++i) {
         if (P->free_tickets.empty()) {
-            return fail(TRI_EAGAIN, "max_outstanding=%u tickets alive", P->cfg.max_outstanding);
+            return tri_fail(TRI_EAGAIN, "max_outstanding=%u tickets alive", P->cfg.max_outstanding);
         }
         enqueue_locked(P, &q[i], &out[i]);
         if (n_done) *n_done = i + 1;
@@ -873,11 +860,11 @@ extern "C" int search_submit_batch_dev(tri_pool *P, const tri_index *index, cons
                                        const uint32_t *klass, tri_ticket *out, uint32_t *n_done)
 {
     if (n_done) *n_done = 0;
-    if (!P || !index || (n && (!vecs || !k || !nprobe || !metric || !klass || !out))) return fail(TRI_EINVAL, "NULL argument");
+    if (!P || !index || (n && (!vecs || !k || !nprobe || !metric || !klass || !out))) return tri_fail(TRI_EINVAL, "NULL argument");
     std::lock_guard<std::mutex> lk(P->mu);
     const uint32_t es = esize(index->p.dtype);
     if (pitch_bytes % es || pitch_bytes < (uint64_t)index->p.dim * es || (uintptr_t)vecs % es)
-        return fail(TRI_EINVAL, "pitch_bytes / vecs must be multiples of the element size and cover dim elements");
+        return tri_fail(TRI_EINVAL, "pitch_bytes / vecs must be multiples of the element size and cover dim elements");
     tri_query q{};
     q.index = index;
     q.vec = vecs;
@@ -887,7 +874,7 @@ extern "C" int search_submit_batch_dev(tri_pool *P, const tri_index *index, cons
         if (rc) return rc;
     }
     for (uint32_t i = 0; i < n; ++i) {
-        if (P->free_tickets.empty()) return fail(TRI_EAGAIN, "max_outstanding=%u tickets alive", P->cfg.max_outstanding);
+        if (P->free_tickets.empty()) return tri_fail(TRI_EAGAIN, "max_outstanding=%u tickets alive", P->cfg.max_outstanding);
         const uint32_t ti = P->free_tickets.back();
         P->free_tickets.pop_back();
         Ticket &t = P->tickets[ti];
@@ -908,7 +895,7 @@ extern "C" int search_submit_batch_dev(tri_pool *P, const tri_index *index, cons
 
 extern "C" int search_submit(tri_pool *P, const tri_query *q, tri_ticket *out)
 {
-    if (!q || !out) return fail(TRI_EINVAL, "NULL argument");
+    if (!q || !out) return tri_fail(TRI_EINVAL, "NULL argument");
     return search_submit_batch(P, q, 1, out, nullptr);
 }
 
@@ -985,9 +972,9 @@ int record_step(tri_pool *P, StepRec &R, const TriDevWs &W, bool keep_probes, ui
     const uint32_t group_rows = std::min(P->coarse_rows, sh.slots);
     hipError_t e = tri_scan_prepare(P->attached_row_bytes, P->scan_class_mask);
     if (e == hipSuccess) e = tri_coarse_prepare();
-    if (e != hipSuccess) return fail(TRI_EHIP, "kernel set-up -> %s", hipGetErrorString(e));
+    if (e != hipSuccess) return tri_fail(TRI_EHIP, "kernel set-up -> %s", hipGetErrorString(e));
     e = hipStreamBeginCapture(s, hipStreamCaptureModeThreadLocal);
-    if (e != hipSuccess) return fail(TRI_EHIP, "hipStreamBeginCapture -> %s (a pool with TRI_FLAG_GRAPH needs a stream of its own, not the default stream)", hipGetErrorString(e));
+    if (e != hipSuccess) return tri_fail(TRI_EHIP, "hipStreamBeginCapture -> %s (a pool with TRI_FLAG_GRAPH needs a stream of its own, not the default stream)", hipGetErrorString(e));
     e = tri_launch_pull_block(s, P->ws.upload, R.up_dev,
                               sizeof(TriStepHdr) + (size_t)sh.slots * (sizeof(TriNewDesc) + sizeof(TriPlanEntry)) + 512);
     if (e == hipSuccess) e = tri_launch_admit(P->ctx, P->ws, sh.slots);
@@ -1005,13 +992,13 @@ int record_step(tri_pool *P, StepRec &R, const TriDevWs &W, bool keep_probes, ui
     const hipError_t e2 = hipStreamEndCapture(s, &g);      // (always: a stream must not be left capturing)
     if (e != hipSuccess || e2 != hipSuccess) {
         if (g) (void)hipGraphDestroy(g);
-        return fail(TRI_EHIP, "recording the step -> %s", hipGetErrorString(e != hipSuccess ? e : e2));
+        return tri_fail(TRI_EHIP, "recording the step -> %s", hipGetErrorString(e != hipSuccess ? e : e2));
     }
     hipGraphExec_t x = nullptr;
     e = hipGraphInstantiate(&x, g, nullptr, nullptr, 0);
     if (e != hipSuccess) {
         (void)hipGraphDestroy(g);
-        return fail(TRI_EHIP, "hipGraphInstantiate -> %s", hipGetErrorString(e));
+        return tri_fail(TRI_EHIP, "hipGraphInstantiate -> %s", hipGetErrorString(e));
     }
     R.graph[b] = g;
     R.graph_exec[b] = x;
@@ -1022,7 +1009,7 @@ int record_step(tri_pool *P, StepRec &R, const TriDevWs &W, bool keep_probes, ui
 
 extern "C" int search_step(tri_pool *P, tri_step_stats *st)
 {
-    if (!P) return fail(TRI_EINVAL, "pool is NULL");
+    if (!P) return tri_fail(TRI_EINVAL, "pool is NULL");
     std::lock_guard<std::mutex> lk(P->mu);
     HIP_TRY(hipSetDevice(P->device));
     tri_step_stats stats{};
@@ -1181,7 +1168,7 @@ extern "C" int search_step(tri_pool *P, tri_step_stats *st)
         uint32_t b = a;
         while (b < n_new && P->tickets[P->newq[b]].index == ix) ++b;
         for (uint32_t c = a; c < b; c += P->coarse_rows) {
-            if (n_groups == TRI_MAX_COARSE_GROUPS) return fail(TRI_EINVAL, "internal: more coarse groups than the step header holds");
+            if (n_groups == TRI_MAX_COARSE_GROUPS) return tri_fail(TRI_EINVAL, "internal: more coarse groups than the step header holds");
             hdr_h->group[n_groups++] = TriCoarseGroup{c, std::min(P->coarse_rows, b - c), ix->id, desc_h[c].row_off};
         }
         a = b;
@@ -1270,12 +1257,12 @@ namespace {
 int poll_locked(tri_pool *P, tri_ticket tk, uint32_t *n_out, int64_t *ids, float *dist, uint32_t room)
 {
     uint32_t ti;
-    if (!ticket_lookup(P, tk, &ti)) return fail(TRI_ENOENT, "unknown ticket");
+    if (!ticket_lookup(P, tk, &ti)) return tri_fail(TRI_ENOENT, "unknown ticket");
     Ticket &t = P->tickets[ti];
-    if (t.cancelled) return fail(TRI_ENOENT, "ticket was cancelled");
+    if (t.cancelled) return tri_fail(TRI_ENOENT, "ticket was cancelled");
     if (t.state != T_DONE) return TRI_EAGAIN;
-    if (!ids || !dist) return fail(TRI_EINVAL, "ids / dist is NULL");
-    if (room < t.k) return fail(TRI_EINVAL, "row of %u entries is too short for k=%u", room, t.k);
+    if (!ids || !dist) return tri_fail(TRI_EINVAL, "ids / dist is NULL");
+    if (room < t.k) return tri_fail(TRI_EINVAL, "row of %u entries is too short for k=%u", room, t.k);
     const uint32_t kmax = P->cfg.kmax;
     for (uint32_t i = 0; i < t.n_out; ++i) {
         ids[i] = (int64_t)P->res_ids[(size_t)ti * kmax + i];
@@ -1293,7 +1280,7 @@ int poll_locked(tri_pool *P, tri_ticket tk, uint32_t *n_out, int64_t *ids, float
 
 extern "C" int search_poll(tri_pool *P, tri_ticket tk, uint32_t *n_out, int64_t *ids, float *dist)
 {
-    if (!P) return fail(TRI_EINVAL, "pool is NULL");
+    if (!P) return tri_fail(TRI_EINVAL, "pool is NULL");
     std::lock_guard<std::mutex> lk(P->mu);
     HIP_TRY(hipSetDevice(P->device));
     int rc = reap(P, false, nullptr);
@@ -1304,7 +1291,7 @@ extern "C" int search_poll(tri_pool *P, tri_ticket tk, uint32_t *n_out, int64_t 
 extern "C" int search_poll_batch(tri_pool *P, const tri_ticket *tk, uint32_t n, uint32_t stride, uint32_t *n_out,
                                  int64_t *ids, float *dist, int *status)
 {
-    if (!P || (n && (!tk || !ids || !dist || !status || !n_out))) return fail(TRI_EINVAL, "NULL argument");
+    if (!P || (n && (!tk || !ids || !dist || !status || !n_out))) return tri_fail(TRI_EINVAL, "NULL argument");
     std::lock_guard<std::mutex> lk(P->mu);
     HIP_TRY(hipSetDevice(P->device));
     int rc = reap(P, false, nullptr);
@@ -1319,13 +1306,13 @@ extern "C" int search_poll_batch(tri_pool *P, const tri_ticket *tk, uint32_t n, 
 
 extern "C" int search_probes(tri_pool *P, tri_ticket tk, uint32_t *lists, uint32_t *n_out)
 {
-    if (!P || !lists) return fail(TRI_EINVAL, "NULL argument");
+    if (!P || !lists) return tri_fail(TRI_EINVAL, "NULL argument");
     std::lock_guard<std::mutex> lk(P->mu);
-    if (!(P->cfg.flags & TRI_FLAG_KEEP_PROBES)) return fail(TRI_EINVAL, "pool was created without TRI_FLAG_KEEP_PROBES");
+    if (!(P->cfg.flags & TRI_FLAG_KEEP_PROBES)) return tri_fail(TRI_EINVAL, "pool was created without TRI_FLAG_KEEP_PROBES");
     uint32_t ti;
-    if (!ticket_lookup(P, tk, &ti)) return fail(TRI_ENOENT, "unknown ticket");
+    if (!ticket_lookup(P, tk, &ti)) return tri_fail(TRI_ENOENT, "unknown ticket");
     Ticket &t = P->tickets[ti];
-    if (t.cancelled) return fail(TRI_ENOENT, "ticket was cancelled");
+    if (t.cancelled) return tri_fail(TRI_ENOENT, "ticket was cancelled");
     if (t.state == T_RETIRING) {
         HIP_TRY(hipSetDevice(P->device));
         int rc = reap(P, false, nullptr);
@@ -1339,12 +1326,12 @@ extern "C" int search_probes(tri_pool *P, tri_ticket tk, uint32_t *lists, uint32
 
 extern "C" int search_cancel(tri_pool *P, tri_ticket tk)
 {
-    if (!P) return fail(TRI_EINVAL, "pool is NULL");
+    if (!P) return tri_fail(TRI_EINVAL, "pool is NULL");
     std::lock_guard<std::mutex> lk(P->mu);
     uint32_t ti;
-    if (!ticket_lookup(P, tk, &ti)) return fail(TRI_ENOENT, "unknown ticket");
+    if (!ticket_lookup(P, tk, &ti)) return tri_fail(TRI_ENOENT, "unknown ticket");
     Ticket &t = P->tickets[ti];
-    if (t.cancelled) return fail(TRI_ENOENT, "ticket was cancelled");
+    if (t.cancelled) return tri_fail(TRI_ENOENT, "ticket was cancelled");
     if (t.state == T_PENDING) {
         std::deque<uint32_t> &Q = P->pending[t.klass];
         Q.erase(std::find(Q.begin(), Q.end(), ti));
@@ -1363,7 +1350,7 @@ extern "C" int search_cancel(tri_pool *P, tri_ticket tk)
 
 extern "C" int search_sync(tri_pool *P)
 {
-    if (!P) return fail(TRI_EINVAL, "pool is NULL");
+    if (!P) return tri_fail(TRI_EINVAL, "pool is NULL");
     std::lock_guard<std::mutex> lk(P->mu);
     HIP_TRY(hipSetDevice(P->device));
     return reap(P, true, nullptr);
@@ -1373,8 +1360,8 @@ extern "C" int search_sync(tri_pool *P)
 extern "C" int tri_policy_split(uint32_t free_slots, uint32_t n_high, uint32_t n_low, float high_share,
                                 uint32_t *take_high, uint32_t *take_low)
 {
-    if (!take_high || !take_low) return fail(TRI_EINVAL, "NULL argument");
-    if (!(high_share >= 0.0f && high_share <= 1.0f)) return fail(TRI_EINVAL, "high_share must lie in [0, 1]");
+    if (!take_high || !take_low) return tri_fail(TRI_EINVAL, "NULL argument");
+    if (!(high_share >= 0.0f && high_share <= 1.0f)) return tri_fail(TRI_EINVAL, "high_share must lie in [0, 1]");
     // the reserved part first, then the other class up to what is left, then the high class again for the rest
     // (a share given as a rounded float must not reserve a slot more than its decimal value says: 0.1 of 30 is 3)
     const uint32_t reserved = (uint32_t)std::min<double>(free_slots, std::ceil((double)high_share * free_slots - 1e-4));
@@ -1388,7 +1375,7 @@ extern "C" int tri_policy_split(uint32_t free_slots, uint32_t n_high, uint32_t n
 extern "C" int tri_policy_slack_order(uint32_t n, const int64_t *deadline_ns, const uint32_t *steps_left, int64_t now_ns_,
                                       int64_t step_ns, uint32_t m, uint32_t *order)
 {
-    if (n && (!deadline_ns || !steps_left || !order)) return fail(TRI_EINVAL, "NULL argument");
+    if (n && (!deadline_ns || !steps_left || !order)) return tri_fail(TRI_EINVAL, "NULL argument");
     if (m > n) m = n;
     std::vector<std::pair<int64_t, uint32_t>> v(n);      // (slack, index); no deadline = latest possible slack
     for (uint32_t i = 0; i < n; ++i) {
@@ -1411,12 +1398,12 @@ extern "C" int tri_policy_slack_order(uint32_t n, const int64_t *deadline_ns, co
 
 extern "C" int search_set_policy(tri_pool *P, const tri_policy *pol)
 {
-    if (!P || !pol) return fail(TRI_EINVAL, "NULL argument");
-    if (!(pol->high_share >= 0.0f && pol->high_share <= 1.0f)) return fail(TRI_EINVAL, "high_share must lie in [0, 1]");
+    if (!P || !pol) return tri_fail(TRI_EINVAL, "NULL argument");
+    if (!(pol->high_share >= 0.0f && pol->high_share <= 1.0f)) return tri_fail(TRI_EINVAL, "high_share must lie in [0, 1]");
     if (pol->order_high != TRI_ORDER_FIFO && pol->order_high != TRI_ORDER_SLACK)
-        return fail(TRI_EINVAL, "order_high must be TRI_ORDER_FIFO or TRI_ORDER_SLACK");
+        return tri_fail(TRI_EINVAL, "order_high must be TRI_ORDER_FIFO or TRI_ORDER_SLACK");
     if (!(pol->flush_timeout_s >= 0.0) || !(pol->flush_timeout_high_s >= 0.0))
-        return fail(TRI_EINVAL, "flush time-outs must not be negative");
+        return tri_fail(TRI_EINVAL, "flush time-outs must not be negative");
     std::lock_guard<std::mutex> lk(P->mu);
     P->policy = *pol;
     return TRI_OK;
@@ -1424,7 +1411,7 @@ extern "C" int search_set_policy(tri_pool *P, const tri_policy *pol)
 
 extern "C" int search_get_policy(tri_pool *P, tri_policy *pol, double *mean_step_s)
 {
-    if (!P) return fail(TRI_EINVAL, "pool is NULL");
+    if (!P) return tri_fail(TRI_EINVAL, "pool is NULL");
     std::lock_guard<std::mutex> lk(P->mu);
     if (pol) *pol = P->policy;
     if (mean_step_s) *mean_step_s = P->mean_step_s;
@@ -1433,14 +1420,14 @@ extern "C" int search_get_policy(tri_pool *P, tri_policy *pol, double *mean_step
 
 extern "C" int search_set_feedback(tri_pool *P, const tri_feedback_cfg *c)
 {
-    if (!P) return fail(TRI_EINVAL, "pool is NULL");
+    if (!P) return tri_fail(TRI_EINVAL, "pool is NULL");
     std::lock_guard<std::mutex> lk(P->mu);
     if (!c) { P->fb_on = false; return TRI_OK; }
     tri_policy probe = P->policy;
     tri_feedback_signals none{__builtin_nanf(""), __builtin_nanf(""), __builtin_nanf(""), 0.f, __builtin_nan("")};
     if (!(c->period_s >= 0.0) || !(c->wait_p95_budget_s >= 0.0) || !(c->u_kv_band >= 0.0f) ||
         tri_policy_feedback(c, &none, &probe, nullptr) != TRI_OK)
-        return fail(TRI_EINVAL, "feedback configuration out of range (0 <= r_min <= r_max <= 1, r_step > 0, tau_factor > 1, "
+        return tri_fail(TRI_EINVAL, "feedback configuration out of range (0 <= r_min <= r_max <= 1, r_step > 0, tau_factor > 1, "
                                 "0 <= tau_min_s <= tau_max_s, period_s, wait_p95_budget_s, u_kv_band >= 0)");
     P->fb = *c;
     P->fb_on = true;
@@ -1455,9 +1442,9 @@ extern "C" int search_set_feedback(tri_pool *P, const tri_feedback_cfg *c)
 
 extern "C" int search_report_signals(tri_pool *P, float u_kv, float decode_stall)
 {
-    if (!P) return fail(TRI_EINVAL, "pool is NULL");
+    if (!P) return tri_fail(TRI_EINVAL, "pool is NULL");
     if ((u_kv == u_kv && !(u_kv >= 0.0f && u_kv <= 1.0f)) || (decode_stall == decode_stall && !(decode_stall >= 0.0f && decode_stall <= 1.0f)))
-        return fail(TRI_EINVAL, "signals are fractions in [0, 1] (or NaN for unknown)");
+        return tri_fail(TRI_EINVAL, "signals are fractions in [0, 1] (or NaN for unknown)");
     std::lock_guard<std::mutex> lk(P->mu);
     P->fb_u_kv = u_kv;
     P->fb_stall = decode_stall;
@@ -1466,7 +1453,7 @@ extern "C" int search_report_signals(tri_pool *P, float u_kv, float decode_stall
 
 extern "C" int search_get_feedback(tri_pool *P, uint64_t *periods, tri_feedback_signals *last)
 {
-    if (!P) return fail(TRI_EINVAL, "pool is NULL");
+    if (!P) return tri_fail(TRI_EINVAL, "pool is NULL");
     std::lock_guard<std::mutex> lk(P->mu);
     if (periods) *periods = P->fb_periods;
     if (last) *last = P->fb_last;
@@ -1482,18 +1469,18 @@ extern "C" int search_run_stream(tri_pool *P, const tri_query *q, const double *
                                  uint32_t stride, uint32_t *n_out, int64_t *ids, float *dist, double *done_s,
                                  uint32_t *probes, tri_stream_stats *out)
 {
-    if (!P || !q || !arrival_s || !n_out || !ids || !dist || !done_s) return fail(TRI_EINVAL, "NULL argument");
-    if (n == 0) return fail(TRI_EINVAL, "empty stream");
+    if (!P || !q || !arrival_s || !n_out || !ids || !dist || !done_s) return tri_fail(TRI_EINVAL, "NULL argument");
+    if (n == 0) return tri_fail(TRI_EINVAL, "empty stream");
     if (probes && !(P->cfg.flags & TRI_FLAG_KEEP_PROBES))
-        return fail(TRI_EINVAL, "probe lists need a pool created with TRI_FLAG_KEEP_PROBES");
+        return tri_fail(TRI_EINVAL, "probe lists need a pool created with TRI_FLAG_KEEP_PROBES");
     {
         std::lock_guard<std::mutex> lk(P->mu);
-        if (P->free_tickets.size() != P->tickets.size()) return fail(TRI_EINVAL, "the pool has queries in flight");
+        if (P->free_tickets.size() != P->tickets.size()) return tri_fail(TRI_EINVAL, "the pool has queries in flight");
         for (uint32_t i = 0; i < n; ++i) {
             int rc = validate_query(P, &q[i]);
             if (rc) return rc;
-            if (q[i].k > stride) return fail(TRI_EINVAL, "query %u: k=%u exceeds the row stride %u", i, q[i].k, stride);
-            if (i && arrival_s[i] < arrival_s[i - 1]) return fail(TRI_EINVAL, "arrival times must not decrease");
+            if (q[i].k > stride) return tri_fail(TRI_EINVAL, "query %u: k=%u exceeds the row stride %u", i, q[i].k, stride);
+            if (i && arrival_s[i] < arrival_s[i - 1]) return tri_fail(TRI_EINVAL, "arrival times must not decrease");
         }
         P->done_log.clear();
     }
@@ -1528,7 +1515,7 @@ extern "C" int search_run_stream(tri_pool *P, const tri_query *q, const double *
             }
             const double t_col = elapsed();
             acc.submit_s += t_col - t_sub;
-            rc = hipSetDevice(P->device) == hipSuccess ? reap(P, false, nullptr) : fail(TRI_EHIP, "hipSetDevice failed");
+            rc = hipSetDevice(P->device) == hipSuccess ? reap(P, false, nullptr) : tri_fail(TRI_EHIP, "hipSetDevice failed");
             if (rc) break;
             if (!P->done_log.empty()) {              // (reap delivered them into the caller's arrays; here: their time)
                 const double t = elapsed();
@@ -1588,8 +1575,8 @@ extern "C" int search_run_stream(tri_pool *P, const tri_query *q, const double *
 
 extern "C" int tri_pool_set_profiling(tri_pool *P, uint32_t flags)
 {
-    if (!P) return fail(TRI_EINVAL, "pool is NULL");
-    if (flags & ~(uint32_t)(TRI_FLAG_PROFILE | TRI_FLAG_PROFILE_SCAN)) return fail(TRI_EINVAL, "only the profiling flags can be changed");
+    if (!P) return tri_fail(TRI_EINVAL, "pool is NULL");
+    if (flags & ~(uint32_t)(TRI_FLAG_PROFILE | TRI_FLAG_PROFILE_SCAN)) return tri_fail(TRI_EINVAL, "only the profiling flags can be changed");
     std::lock_guard<std::mutex> lk(P->mu);
     P->cfg.flags = (P->cfg.flags & ~(uint32_t)(TRI_FLAG_PROFILE | TRI_FLAG_PROFILE_SCAN)) | flags;
     return TRI_OK;
@@ -1597,8 +1584,8 @@ extern "C" int tri_pool_set_profiling(tri_pool *P, uint32_t flags)
 
 extern "C" int tri_pool_set_replay(tri_pool *P, int on)
 {
-    if (!P) return fail(TRI_EINVAL, "pool is NULL");
-    if (on && !P->stream) return fail(TRI_EINVAL, "a step cannot be recorded on the default stream: give the pool a stream of its own");
+    if (!P) return tri_fail(TRI_EINVAL, "pool is NULL");
+    if (on && !P->stream) return tri_fail(TRI_EINVAL, "a step cannot be recorded on the default stream: give the pool a stream of its own");
     std::lock_guard<std::mutex> lk(P->mu);
     P->cfg.flags = on ? (P->cfg.flags | TRI_FLAG_GRAPH) : (P->cfg.flags & ~(uint32_t)TRI_FLAG_GRAPH);
     return TRI_OK;
@@ -1606,7 +1593,7 @@ extern "C" int tri_pool_set_replay(tri_pool *P, int on)
 
 extern "C" int tri_pool_kernel_times(tri_pool *P, tri_kernel_times *out, int reset)
 {
-    if (!P || !out) return fail(TRI_EINVAL, "NULL argument");
+    if (!P || !out) return tri_fail(TRI_EINVAL, "NULL argument");
     std::lock_guard<std::mutex> lk(P->mu);
     *out = P->times;
     if (reset) P->times = tri_kernel_times{};
