@@ -336,3 +336,57 @@ def test_argument_errors_and_empty_steps():
     with tg.GraphPool(X, G, np.array([3, 9], dtype=np.uint32), tri.TRI_F32, slots=2, topm=4, parents=1, max_iters=0) as pool:
         ids, dist, n_out, iters, evals, _ = pool.run_all(X[4:5], 4, tri.TRI_L2)
         assert list(ids[0]) == [3, 9, -1, -1] and int(n_out[0]) == 2 and int(iters[0]) == 0 and int(evals[0]) == 2
+
+
+def test_several_threads_submit_while_one_steps():
+    """graph_submit is safe from several threads while one driver thread steps: integer-valued data, so
+    every answer must equal the oracle's exactly, whichever step its request happened to join."""
+    import threading
+    import time
+    tri, tg = _lib()
+    n, dim, D, M, p, iters, nq = 4000, 64, 16, 32, 2, 40, 240
+    Xt, Z = graph_inputs.make_points(n, dim, 8, np.float32, graph_inputs.SEED_POINTS + 9, integer=True)
+    Qt, _ = graph_inputs.make_points(nq, dim, 8, np.float32, graph_inputs.SEED_QUERIES + 9, integer=True)
+    Gt = graph_inputs.make_graph(Z, D, 4, graph_inputs.SEED_EDGES + 9)
+    X, Q, G = Xt.numpy(), Qt.numpy(), Gt.numpy().astype(np.uint32)
+    seeds = graph_inputs.entry_points(n, 16).astype(np.uint32)
+    k = np.random.default_rng(3).integers(1, M + 1, size=nq).astype(np.uint32)
+    metric = (np.arange(nq) % 2).astype(np.uint32)
+    want = _oracle_all(X, G, seeds, Q, k, metric, M, p, iters)
+    n_threads = 4
+    with tg.GraphPool(X, G, seeds, tri.TRI_F32, slots=24, topm=M, parents=p, max_iters=iters, max_outstanding=1024,
+                      groups=3) as pool:
+        tickets = np.zeros(nq, dtype=np.uint64)
+        errors = []
+
+        def submitter(w):
+            try:
+                mine = np.arange(w, nq, n_threads)
+                for c0 in range(0, mine.size, 5):
+                    sel = mine[c0:c0 + 5]
+                    t, rc = pool.submit(np.ascontiguousarray(Q[sel]), k[sel], metric[sel])
+                    assert rc == tri.TRI_OK and t.shape[0] == sel.size
+                    tickets[sel] = t
+                    time.sleep(0.0005)
+            except Exception as e:          # (reported by the main thread)
+                errors.append(e)
+
+        threads = [threading.Thread(target=submitter, args=(w,)) for w in range(n_threads)]
+        for th in threads:
+            th.start()
+        steps = 0
+        while True:
+            st = pool.step()
+            steps += 1
+            assert steps < 500000, "graph_step loop did not drain"
+            if not any(th.is_alive() for th in threads) and st.running == 0 and st.pending == 0:
+                break
+        for th in threads:
+            th.join()
+        assert not errors, errors
+        pool.sync()
+        assert len(set(tickets.tolist())) == nq, "a ticket was handed out twice"
+        ids, dist, n_out, it, ev, status = pool.poll(tickets, M)
+        assert np.all(status == tri.TRI_OK)
+        _say(f"4 submitters, {steps} steps")
+        _check_exact((ids, dist, n_out, it, ev), want, k)

@@ -813,3 +813,58 @@ def test_massive_ties_take_the_exact_path():
             ids, dist, n_out, probes, _ = harness.run_all(tri, pool, q)
             # integer-valued data + quarter offsets: every score is exact in fp32 -> strict comparison
             harness.compare_with_oracle(oidx, base, queries, k, nprobe, metric, ids, dist, n_out, probes, strict=True)
+
+
+def test_several_threads_submit_while_one_steps():
+    """search_submit_batch is safe from several threads while one driver thread steps and polls: four
+    submitters feed their shares in small chunks; every query is answered once and as the oracle says."""
+    import threading
+    import time
+    tri = harness.lib()
+    cfg = workloads.CONFIGS[0].scaled(n_base=20_000, n_components=64, nlist=96, n_queries=400)
+    base, queries, rows = workloads.make_config01(cfg)
+    k = np.random.default_rng(5).integers(1, 40, size=cfg.n_queries).astype(np.uint32)
+    nprobe = np.random.default_rng(6).integers(1, 33, size=cfg.n_queries).astype(np.uint32)
+    metric = (np.arange(cfg.n_queries) % 2).astype(np.uint32)
+    klass = (np.arange(cfg.n_queries) % 3 == 0).astype(np.uint32)
+    n_threads = 4
+    with harness.default_pool(tri, max_dim=cfg.dim, slots=48, lists_per_query_step=4) as pool:
+        idx = _build_f32(tri, pool, cfg, base, rows)
+        q = tri.make_queries(idx, queries, k, nprobe, metric, klass)
+        tickets = np.zeros(cfg.n_queries, dtype=np.uint64)
+        errors = []
+
+        def submitter(w):
+            try:
+                mine = np.arange(w, cfg.n_queries, n_threads)
+                for c0 in range(0, mine.size, 7):
+                    sel = mine[c0:c0 + 7]
+                    t, rc = tri.search_submit_batch(pool.handle, np.ascontiguousarray(q[sel]))
+                    assert rc == tri.TRI_OK and t.shape[0] == sel.size
+                    tickets[sel] = t
+                    time.sleep(0.0005)
+            except Exception as e:          # (reported by the main thread)
+                errors.append(e)
+
+        threads = [threading.Thread(target=submitter, args=(w,)) for w in range(n_threads)]
+        for th in threads:
+            th.start()
+        steps = 0
+        while True:
+            st = tri.search_step(pool.handle)
+            steps += 1
+            assert steps < 200000, "search_step loop did not drain"
+            alive = any(th.is_alive() for th in threads)
+            if not alive and st.running == 0 and st.pending_high == 0 and st.pending_low == 0 and st.items == 0:
+                break
+        for th in threads:
+            th.join()
+        assert not errors, errors
+        tri.search_sync(pool.handle)
+        assert len(set(tickets.tolist())) == cfg.n_queries, "a ticket was handed out twice"
+        probes = [tri.search_probes(pool.handle, int(tickets[i]), int(nprobe[i])) for i in range(cfg.n_queries)]
+        ids, dist, n_out, status = tri.search_poll_batch(pool.handle, tickets, int(k.max()))
+        assert np.all(status == tri.TRI_OK)
+        oidx = harness.oracle_index(tri, idx, base)
+        rep = harness.compare_with_oracle(oidx, base, queries, k, nprobe, metric, ids, dist, n_out, probes)
+        _say(f"4 submitters, {steps} steps: {rep}")
