@@ -140,7 +140,9 @@ int ivf_info(const tri_index *index, uint64_t *n, uint32_t *dim, uint32_t *nlist
              uint32_t *max_list_len);
 
 /* Detach and forget the index (its dev_mem returns to the caller).  TRI_EINVAL while the pool
- * has queries in flight. */
+ * has queries in flight.  Finished results of its queries that have not been polled yet stay pollable; its
+ * place in the pool (and, if it was the index attached last, its range of the list table) is free for the
+ * next ivf_build; a later submit that still names the handle is refused with TRI_EINVAL. */
 int ivf_destroy(tri_index *index);
 
 /* ---------------------------------------------------------------------------------------

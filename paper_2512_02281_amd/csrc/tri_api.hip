@@ -404,9 +404,22 @@ bool ticket_lookup(tri_pool *P, tri_ticket t, uint32_t *idx)
     return true;
 }
 
-int validate_query(tri_pool *P, const tri_query *q)
+// (compared as a pointer against the pool's table first: a handle of a destroyed index is never read)
+bool is_attached(const tri_pool *P, const tri_index *ix)
 {
-    if (!q->index || q->index->pool != P) return tri_fail(TRI_EINVAL, "query.index is not attached to this pool");
+    if (!ix) return false;
+    for (const tri_index *a : P->indexes)
+        if (a == ix) return true;
+    return false;
+}
+
+// *known: the index of the previous query that passed (a batch mostly names one index; NULL at first)
+int validate_query(tri_pool *P, const tri_query *q, const tri_index **known)
+{
+    if (q->index != *known) {
+        if (!is_attached(P, q->index)) return tri_fail(TRI_EINVAL, "query.index is not attached to this pool");
+        *known = q->index;
+    }
     if (!q->vec) return tri_fail(TRI_EINVAL, "query.vec is NULL");
     if (q->k == 0 || q->k > P->cfg.kmax) return tri_fail(TRI_EINVAL, "k=%u outside 1..%u", q->k, P->cfg.kmax);
     if (q->nprobe == 0 || q->nprobe > P->cfg.nprobe_max || q->nprobe > q->index->p.nlist)
@@ -841,9 +854,10 @@ extern "C" int search_submit_batch(tri_pool *P, const tri_query *q, uint32_t n, 
     if (n_done) *n_done = 0;
     if (!P || (!q && n) || (!out && n)) return tri_fail(TRI_EINVAL, "NULL argument");
     std::lock_guard<std::mutex> lk(P->mu);
+    const tri_index *known = nullptr;
     for (uint32_t i = 0; i < n; ++i) {
-        int rc = validate_query(P, &q[i]);
-        if (rc) return rc;          // nothing of this call has been queued yet only if i == 0; report progress
+        int rc = validate_query(P, &q[i], &known);
+        if (rc) return rc;          // (nothing of this call has been queued)
     }
     for (uint32_t i = 0; i < n; ++i) {
         if (P->free_tickets.empty()) {
@@ -862,15 +876,17 @@ extern "C" int search_submit_batch_dev(tri_pool *P, const tri_index *index, cons
     if (n_done) *n_done = 0;
     if (!P || !index || (n && (!vecs || !k || !nprobe || !metric || !klass || !out))) return tri_fail(TRI_EINVAL, "NULL argument");
     std::lock_guard<std::mutex> lk(P->mu);
+    if (!is_attached(P, index)) return tri_fail(TRI_EINVAL, "index is not attached to this pool");
     const uint32_t es = esize(index->p.dtype);
     if (pitch_bytes % es || pitch_bytes < (uint64_t)index->p.dim * es || (uintptr_t)vecs % es)
         return tri_fail(TRI_EINVAL, "pitch_bytes / vecs must be multiples of the element size and cover dim elements");
     tri_query q{};
     q.index = index;
     q.vec = vecs;
+    const tri_index *known = index;
     for (uint32_t i = 0; i < n; ++i) {
         q.k = k[i]; q.nprobe = nprobe[i]; q.metric = metric[i]; q.klass = klass[i];
-        int rc = validate_query(P, &q);
+        int rc = validate_query(P, &q, &known);
         if (rc) return rc;
     }
     for (uint32_t i = 0; i < n; ++i) {
@@ -1476,8 +1492,9 @@ extern "C" int search_run_stream(tri_pool *P, const tri_query *q, const double *
     {
         std::lock_guard<std::mutex> lk(P->mu);
         if (P->free_tickets.size() != P->tickets.size()) return tri_fail(TRI_EINVAL, "the pool has queries in flight");
+        const tri_index *known = nullptr;
         for (uint32_t i = 0; i < n; ++i) {
-            int rc = validate_query(P, &q[i]);
+            int rc = validate_query(P, &q[i], &known);
             if (rc) return rc;
             if (q[i].k > stride) return tri_fail(TRI_EINVAL, "query %u: k=%u exceeds the row stride %u", i, q[i].k, stride);
             if (i && arrival_s[i] < arrival_s[i - 1]) return tri_fail(TRI_EINVAL, "arrival times must not decrease");

@@ -868,3 +868,75 @@ def test_several_threads_submit_while_one_steps():
         oidx = harness.oracle_index(tri, idx, base)
         rep = harness.compare_with_oracle(oidx, base, queries, k, nprobe, metric, ids, dist, n_out, probes)
         _say(f"4 submitters, {steps} steps: {rep}")
+
+
+@pytest.mark.parametrize("recorded", [False, True])
+def test_indexes_come_and_go_in_a_living_pool(recorded):
+    """Indexes are destroyed and built while the pool lives: finished, unpolled results of a destroyed index
+    stay pollable; a new index of another row class takes the freed place (and, when it was the last one
+    attached, its list range); the first index leaves a hole in the list table that later steps must skip.
+    After every change the surviving and the new indexes answer as the oracle says -- also with recorded
+    steps, which have to be recorded afresh whenever the set of attached indexes changes."""
+    tri = harness.lib()
+    cfg_a = workloads.CONFIGS[0].scaled(n_base=12_000, n_components=32, nlist=64, n_queries=50)
+    cfg_b = workloads.CONFIGS[2].scaled(n_base=9_000, n_components=32, nlist=32, n_queries=50, dim=96)
+    cfg_c = workloads.CONFIGS[0].scaled(n_base=7_000, n_components=16, nlist=48, n_queries=50, dim=200)
+    cfg_d = workloads.CONFIGS[0].scaled(n_base=3_000, n_components=8, nlist=16, n_queries=50, dim=40)
+    base_a, q_a, rows_a = workloads.make_config01(cfg_a)
+    base_b_t, base_b, q_b, rows_b = _f16_setup(tri, cfg_b)
+    base_c, q_c, rows_c = workloads.make_config01(cfg_c)
+    base_d, q_d, rows_d = workloads.make_config01(cfg_d)
+    flags = tri.TRI_FLAG_KEEP_PROBES | (tri.TRI_FLAG_GRAPH if recorded else 0)
+
+    def check(pool, parts):
+        """parts: list of (index handle, oracle index, base, queries, k, nprobe, metric); one mixed run."""
+        qs = np.concatenate([tri.make_queries(ix, q, k, npb, m) for ix, _, _, q, k, npb, m in parts])
+        order = np.random.default_rng(3).permutation(qs.shape[0])
+        ids, dist, n_out, probes, _ = harness.run_all(tri, pool, np.ascontiguousarray(qs[order]), submit_chunks=[7, 40, 9])
+        inv = np.argsort(order)
+        ids, dist, n_out, probes = ids[inv], dist[inv], n_out[inv], [probes[i] for i in inv]
+        at = 0
+        for ix, oidx, base, q, k, npb, m in parts:
+            n = q.shape[0]
+            harness.compare_with_oracle(oidx, base, q, k, npb, m, ids[at:at + n], dist[at:at + n], n_out[at:at + n],
+                                        probes[at:at + n])
+            at += n
+
+    with harness.default_pool(tri, slots=24, max_dim=256, max_outstanding=512, lists_per_query_step=3,
+                              max_total_lists=160, max_nlist=64, flags=flags) as pool:
+        ia = pool.build_index(base_a, cfg_a.dim, cfg_a.nlist, tri.TRI_F32, tri.TRI_L2, 4, centroids=base_a[rows_a])
+        ib = pool.build_index(base_b_t, cfg_b.dim, cfg_b.nlist, tri.TRI_F16, tri.TRI_IP, 4,
+                              centroids=base_b[rows_b].astype(np.float32))
+        oa, ob = harness.oracle_index(tri, ia, base_a), harness.oracle_index(tri, ib, base_b)
+        part_a = (ia, oa, base_a, q_a, 10, 12, tri.TRI_L2)
+        _say("lifecycle: A + B")
+        check(pool, [part_a, (ib, ob, base_b, q_b, 7, 9, tri.TRI_IP)])
+        # results of B that nobody has polled yet outlive B
+        qb = tri.make_queries(ib, q_b, 7, 9, tri.TRI_IP)
+        tb, rc = tri.search_submit_batch(pool.handle, qb)
+        assert rc == tri.TRI_OK
+        for _ in range(1000):
+            st = tri.search_step(pool.handle)
+            if st.running == 0 and st.pending_high == 0 and st.pending_low == 0 and st.items == 0:
+                break
+        tri.search_sync(pool.handle)
+        probes_b = [tri.search_probes(pool.handle, int(t), 9) for t in tb]
+        pool.destroy_index(ib)
+        ids, dist, n_out, status = tri.search_poll_batch(pool.handle, tb, 7)
+        assert np.all(status == tri.TRI_OK)
+        harness.compare_with_oracle(ob, base_b, q_b, 7, 9, tri.TRI_IP, ids, dist, n_out, probes_b)
+        # C (another row class) takes B's place and B's list range
+        ic = pool.build_index(base_c, cfg_c.dim, cfg_c.nlist, tri.TRI_F32, tri.TRI_L2, 4, centroids=base_c[rows_c])
+        oc = harness.oracle_index(tri, ic, base_c)
+        part_c = (ic, oc, base_c, q_c, 5, 48, tri.TRI_IP)          # every list probed, the other metric
+        _say("lifecycle: A + C")
+        check(pool, [part_a, part_c])
+        # A goes: its 64 lists stay a hole at the head of the table; D joins behind C
+        pool.destroy_index(ia)
+        idd = pool.build_index(base_d, cfg_d.dim, cfg_d.nlist, tri.TRI_F32, tri.TRI_L2, 4, centroids=base_d[rows_d])
+        od = harness.oracle_index(tri, idd, base_d)
+        _say("lifecycle: C + D")
+        check(pool, [part_c, (idd, od, base_d, q_d, 12, 5, tri.TRI_L2)])
+        # a query for an index that is gone is refused
+        with pytest.raises(Exception):
+            tri.search_submit_batch(pool.handle, tri.make_queries(ia, q_a[:1], 1, 1, 0))
