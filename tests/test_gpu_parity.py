@@ -940,3 +940,31 @@ def test_indexes_come_and_go_in_a_living_pool(recorded):
         # a query for an index that is gone is refused
         with pytest.raises(Exception):
             tri.search_submit_batch(pool.handle, tri.make_queries(ia, q_a[:1], 1, 1, 0))
+
+
+def test_largest_k_and_nprobe():
+    """The limits of the boundary together (TRI_KMAX_LIMIT, TRI_NPROBE_LIMIT): k = 1024 and nprobe = 1024 = nlist
+    (every list probed: the result must be exact kNN by brute force), and neighbours of those limits, on many
+    short lists."""
+    tri = harness.lib()
+    rng = np.random.default_rng(33)
+    n, dim, nlist, nq = 40_000, 32, 1024, 24
+    centres = rng.standard_normal((nlist, dim)).astype(np.float32) * 3
+    base = (centres[rng.integers(0, nlist, size=n)] + rng.standard_normal((n, dim))).astype(np.float32)
+    queries = (centres[rng.integers(0, nlist, size=nq)] + rng.standard_normal((nq, dim))).astype(np.float32)
+    k = np.array([1024, 1000, 1], dtype=np.uint32)[np.arange(nq) % 3]
+    nprobe = np.array([1024, 1024, 1023, 700], dtype=np.uint32)[np.arange(nq) % 4]
+    metric = (np.arange(nq) // 2 % 2).astype(np.uint32)
+    with harness.default_pool(tri, slots=8, items_per_step=8 * 1024, kmax=1024, nprobe_max=1024, max_dim=dim,
+                              max_nlist=nlist, max_total_lists=nlist, score_capacity=64 << 20) as pool:
+        idx = pool.build_index(base, dim, nlist, tri.TRI_F32, tri.TRI_L2, 3, centroids=centres)
+        oidx = harness.oracle_index(tri, idx, base)
+        q = tri.make_queries(idx, queries, k, nprobe, metric)
+        ids, dist, n_out, probes, stats = harness.run_all(tri, pool, q)
+        rep = harness.compare_with_oracle(oidx, base, queries, k, nprobe, metric, ids, dist, n_out, probes)
+        _say(f"largest k and nprobe: {len(stats)} steps, parity {rep}")
+        for i in np.nonzero(nprobe == nlist)[0]:
+            # (as sets, and up to a swap at the k-th place: fp32 and fp64 may order two near-equal scores differently)
+            true_ids, _ = bruteforce.knn(base, queries[i:i + 1], int(k[i]), int(metric[i]))
+            common = len(set(ids[i, :k[i]].tolist()) & set(true_ids[0].tolist()))
+            assert common >= int(k[i]) - 1, f"query {i}: nprobe = nlist must be exact kNN ({common} of {k[i]})"
