@@ -581,13 +581,16 @@ __global__ __launch_bounds__(TRI_SEL_THREADS) void coarse_select_kernel(
             uint32_t *mins = (uint32_t *)sh.pool;
             mins[tid] = best;
             __syncthreads();
-            uint32_t rank = 0;
+            // (the nprobe-th smallest VALUE is the largest one with fewer than nprobe strictly smaller ones:
+            // one comparison per pair, no tie-break needed)
+            if (tid == 0) sh.tmax = 0u;
+            uint32_t below = 0;
             for (uint32_t j = 0; j < TRI_SEL_THREADS; j += 4) {
                 const uint4 y = *(const uint4 *)(mins + j);
-                rank += (y.x < best || (y.x == best && j < tid)) + (y.y < best || (y.y == best && j + 1 < tid)) +
-                        (y.z < best || (y.z == best && j + 2 < tid)) + (y.w < best || (y.w == best && j + 3 < tid));
+                below += (y.x < best) + (y.y < best) + (y.z < best) + (y.w < best);
             }
-            if (rank == d.nprobe - 1) sh.tmax = best;
+            __syncthreads();                                          // (the bound starts at zero)
+            if (below < d.nprobe) atomicMax(&sh.tmax, best);
             __syncthreads();
             const uint32_t bound = sh.tmax;
             __syncthreads();                                          // (mins is read: the pool may be written)
