@@ -8,6 +8,14 @@
   beyond ``check_index`` and the objective comparison.
 * ``check_index``: validates an exported index (partition of the rows, monotone offsets,
   every checked row stored in the list of its best centroid or of one within tolerance).
+
+Pins (tests/test_index_oracle_pins.py, tests/golden/index_examples.json): ``lloyd`` and
+``inertia`` against hand-worked iterations (an empty cluster, the spherical variant) and
+against scipy's k-means on separated blobs; ``assign_rows`` against hand cases with tied
+centroids and an enumeration in Python integers; ``partition`` against counted lists;
+``build_index`` against the lists of the hand-worked search examples; ``check_index`` against
+planted faults (wrong list, worst list, duplicated id, broken offsets, a near-tie on either
+side of the tolerance); and mutated copies of this file, which must fail those pins.
 """
 from __future__ import annotations
 
