@@ -143,10 +143,12 @@ def test_config2_fp16_inner_product_heterogeneous(scale):
         _say(f"config 2 {scale}: index check {rep}, longest list {tri.ivf_info(idx)['max_list_len']}")
         q = tri.make_queries(idx, queries, k, nprobe, tri.TRI_IP)
         ids, dist, n_out, probes, stats = harness.run_all(tri, pool, q)
-        sample = None if scale == "scaled" else np.random.default_rng(5).choice(cfg.n_queries, 96, replace=False)
+        sample = None if scale == "scaled" else np.sort(np.random.default_rng(5).choice(cfg.n_queries, 640, replace=False))
         _say(f"config 2 {scale}: {len(stats)} steps; compare")
-        rep = harness.compare_with_oracle(oidx, base, queries, k, nprobe, 1, ids, dist, n_out, probes, sample=sample)
+        rep = harness.compare_with_oracle(oidx, base, queries, k, nprobe, 1, ids, dist, n_out, probes, sample=sample,
+                                          batch_first=scale == "full")
         _say(f"config 2 {scale}: parity {rep}")
+        assert rep["checked"] == (cfg.n_queries if sample is None else sample.size)
         # the unit-norm identity: the same queries under L2 return the same neighbours (outside ties)
         sub = np.arange(0, cfg.n_queries, max(1, cfg.n_queries // 64))[:64]
         sub_vecs = np.ascontiguousarray(queries[sub])      # must outlive the submit: records hold pointers
@@ -681,7 +683,7 @@ def test_config3_stream_over_two_indexes(scale):
         n, slots, rate, n_check = 3000, 256, 2.0e5, 120
     else:
         rag_cfg, cache_cfg = workloads.CONFIGS[2], workloads.CACHE_INDEX
-        n, slots, rate, n_check = 100_000, 4096, 4.0e5, 96
+        n, slots, rate, n_check = 100_000, 4096, 4.0e5, 1088
     _say(f"config 3 {scale}: generate")
     w = workloads.make_config3(n, "cuda", rag_cfg, cache_cfg)
     torch.cuda.synchronize()
@@ -722,8 +724,9 @@ def test_config3_stream_over_two_indexes(scale):
             oidx = harness.oracle_index(tri, idx, base)
             pl = [probes[i, :w["nprobe"][i]] for i in range(n)]
             rep = harness.compare_with_oracle(oidx, base, queries, w["k"], w["nprobe"], 1, ids, dist, n_out, pl,
-                                              sample=sample)
+                                              sample=sample, batch_first=True)
             _say(f"config 3 {scale}: {name} parity {rep}")
+            assert rep["checked"] == sample.size
             if name == "cache":
                 # hit flag against the oracle's top-1 score
                 flips = 0
@@ -743,8 +746,9 @@ def test_config3_stream_over_two_indexes(scale):
 def test_config4_full_size_in_the_benchmark_configuration():
     """Configuration 4 at full size (10M x 768 fp16, nlist 16384, 4096 queries, nprobe 64, k 100) in
     the launch configuration the benchmark times (4096 slots, one step per batch, device-resident
-    query vectors): a seeded sample of queries is checked one by one against the oracle, every
-    query against the properties that hold at any size."""
+    query vectors): a seeded sample of more than 512 queries is checked against the oracle (the oracle side in
+    one multi-threaded call, the tie-aware checker for every query whose result is not exactly the oracle's),
+    every query against the properties that hold at any size."""
     import torch
     tri = harness.lib()
     cfg = workloads.CONFIGS[4]
@@ -766,10 +770,7 @@ def test_config4_full_size_in_the_benchmark_configuration():
         st = tri.search_step(pool.handle)
         assert st.admitted == Q and st.retired == Q and st.items == Q * cfg.nprobe     # one launch per batch
         tri.search_sync(pool.handle)
-        sample = np.sort(np.random.default_rng(44).choice(Q, 40, replace=False))
-        probes = [None] * Q
-        for i in sample:
-            probes[i] = tri.search_probes(pool.handle, int(tickets[i]), cfg.nprobe)
+        probes = [tri.search_probes(pool.handle, int(tickets[i]), cfg.nprobe) for i in range(Q)]
         ids, dist, n_out, status = tri.search_poll_batch(pool.handle, tickets, cfg.k)
         assert np.all(status == tri.TRI_OK)
         # properties for every query
@@ -784,9 +785,19 @@ def test_config4_full_size_in_the_benchmark_configuration():
         oidx = harness.oracle_index(tri, idx, base)
         rep = oindex.check_index(oidx, oracle.METRIC_IP, tol=2e-3, sample=512, seed=3)
         _say(f"config 4: index check {rep}")
+        # the sample: 512 seeded queries, plus queries that probe the longest list and the shortest ones (among them
+        # lists shorter than the 64-vector sample the thresholds are taken from, if the index has any)
+        lens = np.diff(oidx.list_off).astype(np.int64)
+        pm = np.stack(probes)
+        extreme = np.r_[np.argsort(lens, kind="stable")[:8], np.argmax(lens)]
+        extra = np.concatenate([np.flatnonzero((pm == l).any(axis=1))[:8] for l in extreme])
+        sample = np.unique(np.r_[np.random.default_rng(44).choice(Q, 512, replace=False), extra])
+        _say(f"config 4: list lengths {lens.min()}..{lens.max()}; {sample.size} queries against the oracle "
+             f"({extra.size} of them probe a shortest or the longest list)")
         rep = harness.compare_with_oracle(oidx, base, queries, cfg.k, cfg.nprobe, 1, ids, dist, n_out, probes,
-                                          sample=sample)
+                                          sample=sample, batch_first=True)
         _say(f"config 4: parity {rep}")
+        assert rep["checked"] == sample.size >= 512
         # returned scores of ALL queries against fp64 dot products of the stored vectors
         for i in range(0, Q, 97):
             want = base[ids[i]].astype(np.float64) @ queries[i].astype(np.float64)
