@@ -17,7 +17,9 @@
  *  - every function returns a tri_status (0 = ok, negative = error); nothing throws or aborts
  *    across this boundary; tri_last_error() gives a thread-local text for the last failure.
  *  - pointers marked [host] / [device] / [host|device] say where the memory must live.
- *  - the library never takes ownership of caller memory except where stated (dev_ws, dev_mem).
+ *  - the library never takes ownership of caller memory except where stated (dev_ws, pinned_ws, dev_mem).
+ *  - a HIP failure inside a step leaves the pool marked failed: every later call on it returns
+ *    TRI_EHIP (with the first failure's text) except the destroy calls.
  *  - search_submit* may be called from several threads; search_step / search_poll /
  *    search_sync from one driver thread at a time (calls are serialised by an internal lock).
  *  - argument errors return TRI_EINVAL and change no state.
@@ -85,15 +87,22 @@ typedef struct {
     void *hip_stream;              /* hipStream_t all work is enqueued on (NULL = the null stream)          */
 } tri_pool_cfg;
 
-/* Bytes of device workspace a pool with this configuration needs (256-byte aligned start). */
-int tri_pool_workspace_bytes(const tri_pool_cfg *cfg /*[host]*/, size_t *dev_bytes /*[host] out*/);
+/* Bytes a pool with this configuration needs: dev_bytes of device workspace (256-byte aligned start) and
+ * pinned_host_bytes of page-locked host memory (upload and result blocks of the steps in flight and a store
+ * of max_outstanding padded query rows).  pinned_host_bytes may be NULL. */
+int tri_pool_workspace_bytes(const tri_pool_cfg *cfg /*[host]*/, size_t *dev_bytes /*[host] out*/,
+                             size_t *pinned_host_bytes /*[host] out or NULL*/);
 
-/* Create a pool on the current HIP device.  dev_ws [device]: at least the size reported above,
- * owned by the pool until tri_pool_destroy (the caller frees it afterwards).  Pinned host
- * memory is allocated here (hipHostMalloc): upload and result blocks for the steps in flight and
- * a store of max_outstanding padded query rows; no device memory is allocated by the pool. */
+/* Create a pool on the current HIP device.  All memory is the caller's:
+ *  dev_ws [device]: at least dev_bytes as reported above, 256-byte aligned; owned by the pool until
+ *      tri_pool_destroy (the caller frees it afterwards).
+ *  pinned_ws [host, page-locked and mapped for the device: hipHostMalloc, a torch tensor with
+ *      pin_memory=True] of at least pinned_host_bytes, 256-byte aligned; owned by the pool until
+ *      tri_pool_destroy; TRI_EINVAL if the device cannot address it.  NULL: the pool allocates that much
+ *      with hipHostMalloc itself and frees it in tri_pool_destroy.
+ * No device memory is ever allocated by the pool. */
 int tri_pool_create(const tri_pool_cfg *cfg /*[host]*/, void *dev_ws /*[device]*/, size_t dev_ws_bytes,
-                    tri_pool **out /*[host] out*/);
+                    void *pinned_ws /*[host, pinned] or NULL*/, size_t pinned_ws_bytes, tri_pool **out /*[host] out*/);
 
 /* Destroy the pool.  Waits for enqueued work; every ticket becomes invalid.  Indexes attached
  * to it must be destroyed first (TRI_EINVAL otherwise). */
@@ -116,6 +125,10 @@ typedef struct {
 /* Device bytes the finished index occupies for n base vectors. */
 int ivf_build_bytes(const ivf_params *p /*[host]*/, uint64_t n, size_t *dev_bytes /*[host] out*/);
 
+/* Device bytes of temporary memory ivf_build needs for these parameters (training copy, score blocks,
+ * assignment tables; base_on_host != 0 adds a device copy of the base). */
+int ivf_build_tmp_bytes(const ivf_params *p /*[host]*/, uint64_t n, int base_on_host, size_t *tmp_bytes /*[host] out*/);
+
 /* Build an index and attach it to the pool.
  *  base [host|device]: row-major n x dim, of p->dtype; copied and reordered list by list, the
  *      caller may free it when the call returns.
@@ -123,11 +136,14 @@ int ivf_build_bytes(const ivf_params *p /*[host]*/, uint64_t n, size_t *dev_byte
  *      chosen from p->seed.  Training uses all rows when n <= 256*nlist, otherwise a fixed
  *      pseudo-random subset of 256*nlist rows; an empty cluster keeps its centroid.
  *  dev_mem [device]: ivf_build_bytes() bytes, 256-byte aligned; owned by the index until
- *      ivf_destroy.  Temporary build memory is allocated and freed inside the call.
+ *      ivf_destroy.
+ *  tmp_dev [device]: ivf_build_tmp_bytes() bytes of scratch, 256-byte aligned, free again when the
+ *      call returns (TRI_ENOMEM if too small).  NULL: the call allocates its temporary memory with
+ *      hipMalloc and frees it before it returns.
  * Synchronous.  Must not run while the pool has queries in flight (TRI_EINVAL). */
 int ivf_build(tri_pool *pool, const ivf_params *p /*[host]*/, const void *base /*[host|device]*/, uint64_t n,
               const float *centroids /*[host] or NULL*/, void *dev_mem /*[device]*/, size_t dev_mem_bytes,
-              tri_index **out /*[host] out*/);
+              void *tmp_dev /*[device] or NULL*/, size_t tmp_bytes, tri_index **out /*[host] out*/);
 
 /* Copy the searchable content of an index to host arrays: centroids [nlist x dim] -- exactly the
  * stored values the coarse ranking uses, widened to fp32 --, list_off [nlist+1], list_ids [n]
@@ -171,9 +187,12 @@ int search_submit_batch(tri_pool *pool, const tri_query *q /*[host] n*/, uint32_
 
 /* Queue n queries against ONE index whose vectors already live in device memory (for instance
  * the output of an embedding model on the same GPU).  vecs [device]: n rows of dim elements of the
- * index's dtype, row pitch pitch_bytes (a multiple of the element size); the rows are read by the
- * step that admits each query, so they must stay valid and unchanged until the ticket is finished.
- * k / nprobe / metric / klass: [host] arrays of n.  Same return values as search_submit_batch. */
+ * index's dtype, row pitch pitch_bytes (a multiple of the element size).  The rows are copied into
+ * the pool's own store by a kernel this call enqueues on the pool's stream: like any stream-ordered
+ * operand they must stay valid and unchanged until the stream has passed that point -- work enqueued
+ * on the same stream afterwards may overwrite or free them; another stream, or the host, must wait
+ * for the pool's stream first.  k / nprobe / metric / klass: [host] arrays of n.  Same return values
+ * as search_submit_batch. */
 int search_submit_batch_dev(tri_pool *pool, const tri_index *index, const void *vecs /*[device]*/,
                             uint64_t pitch_bytes, uint32_t n, const uint32_t *k, const uint32_t *nprobe,
                             const uint32_t *metric, const uint32_t *klass, tri_ticket *out /*[host] n*/,
@@ -376,6 +395,12 @@ int tri_pool_set_replay(tri_pool *pool, int on);
  * peak.  dev_sink [device]: 4 writable bytes.  Synchronous. */
 int tri_stream_read_bandwidth(const void *dev_buf, size_t bytes, void *dev_sink, void *hip_stream, uint32_t repeats,
                               double *gb_per_s /*[host] out*/);
+
+/* Testing aid: the next search_step that has work to enqueue fails as if one of its launches had
+ * failed (TRI_EHIP), after it has admitted its queries.  A pool in which a step failed half-way is
+ * marked failed for good: its slot table no longer matches what the GPU holds, so every later call
+ * on it returns TRI_EHIP, except ivf_destroy and tri_pool_destroy, which tear it down. */
+int tri_pool_inject_failure(tri_pool *pool);
 
 const char *tri_last_error(void);
 const char *tri_version(void);

@@ -97,12 +97,13 @@ class tri_stream_stats(ctypes.Structure):
                 ("submit_s", ctypes.c_double), ("step_s", ctypes.c_double), ("collect_s", ctypes.c_double)]
 
 
-EXPORTS = ["tri_pool_workspace_bytes", "tri_pool_create", "tri_pool_destroy", "ivf_build_bytes", "ivf_build",
+EXPORTS = ["tri_pool_workspace_bytes", "tri_pool_create", "tri_pool_destroy", "ivf_build_bytes", "ivf_build_tmp_bytes", "ivf_build",
            "ivf_export", "ivf_info", "ivf_destroy", "search_submit", "search_submit_batch", "search_submit_batch_dev",
            "search_step", "search_poll", "search_poll_batch", "search_probes", "search_cancel", "search_sync",
            "search_run_stream", "search_set_policy", "search_get_policy", "tri_policy_split", "tri_policy_slack_order",
            "tri_policy_feedback", "search_set_feedback", "search_report_signals", "search_get_feedback",
-           "tri_pool_kernel_times", "tri_pool_set_profiling", "tri_pool_set_replay", "tri_stream_read_bandwidth", "tri_last_error", "tri_version"]
+           "tri_pool_kernel_times", "tri_pool_set_profiling", "tri_pool_set_replay", "tri_stream_read_bandwidth",
+           "tri_pool_inject_failure", "tri_last_error", "tri_version"]
 
 
 def _load():
@@ -115,11 +116,13 @@ def _load():
     lib = ctypes.CDLL(LIB_PATH)
     vp, u32, u64, sz = ctypes.c_void_p, ctypes.c_uint32, ctypes.c_uint64, ctypes.c_size_t
     P = ctypes.POINTER
-    lib.tri_pool_workspace_bytes.argtypes = [P(tri_pool_cfg), P(sz)]
-    lib.tri_pool_create.argtypes = [P(tri_pool_cfg), vp, sz, P(vp)]
+    lib.tri_pool_workspace_bytes.argtypes = [P(tri_pool_cfg), P(sz), P(sz)]
+    lib.tri_pool_create.argtypes = [P(tri_pool_cfg), vp, sz, vp, sz, P(vp)]
+    lib.tri_pool_inject_failure.argtypes = [vp]
     lib.tri_pool_destroy.argtypes = [vp]
     lib.ivf_build_bytes.argtypes = [P(ivf_params), u64, P(sz)]
-    lib.ivf_build.argtypes = [vp, P(ivf_params), vp, u64, vp, vp, sz, P(vp)]
+    lib.ivf_build_tmp_bytes.argtypes = [P(ivf_params), u64, ctypes.c_int, P(sz)]
+    lib.ivf_build.argtypes = [vp, P(ivf_params), vp, u64, vp, vp, sz, vp, sz, P(vp)]
     lib.ivf_export.argtypes = [vp, vp, vp, vp]
     lib.ivf_info.argtypes = [vp, P(u64), P(u32), P(u32), P(u32), P(u32)]
     lib.ivf_destroy.argtypes = [vp]
@@ -175,17 +178,24 @@ def _np_ptr(a: Optional[np.ndarray]):
 
 
 # ------------------------------------------------------------------------------------------- pool
-def tri_pool_workspace_bytes(cfg: tri_pool_cfg) -> int:
-    out = ctypes.c_size_t(0)
-    _check(_lib.tri_pool_workspace_bytes(ctypes.byref(cfg), ctypes.byref(out)), "tri_pool_workspace_bytes")
-    return int(out.value)
+def tri_pool_workspace_bytes(cfg: tri_pool_cfg):
+    """(device workspace bytes, pinned host bytes) a pool with this configuration needs."""
+    dev, pinned = ctypes.c_size_t(0), ctypes.c_size_t(0)
+    _check(_lib.tri_pool_workspace_bytes(ctypes.byref(cfg), ctypes.byref(dev), ctypes.byref(pinned)), "tri_pool_workspace_bytes")
+    return int(dev.value), int(pinned.value)
 
 
-def tri_pool_create(cfg: tri_pool_cfg, dev_ws_ptr: int, dev_ws_bytes: int) -> int:
+def tri_pool_create(cfg: tri_pool_cfg, dev_ws_ptr: int, dev_ws_bytes: int, pinned_ptr: Optional[int] = None,
+                    pinned_bytes: int = 0) -> int:
+    """pinned_ptr None: the library allocates the pinned host memory itself."""
     out = ctypes.c_void_p(None)
-    _check(_lib.tri_pool_create(ctypes.byref(cfg), ctypes.c_void_p(dev_ws_ptr), dev_ws_bytes, ctypes.byref(out)),
-           "tri_pool_create")
+    _check(_lib.tri_pool_create(ctypes.byref(cfg), ctypes.c_void_p(dev_ws_ptr), dev_ws_bytes, ctypes.c_void_p(pinned_ptr),
+                                pinned_bytes, ctypes.byref(out)), "tri_pool_create")
     return out.value
+
+
+def tri_pool_inject_failure(pool: int) -> None:
+    _check(_lib.tri_pool_inject_failure(ctypes.c_void_p(pool)), "tri_pool_inject_failure")
 
 
 def tri_pool_destroy(pool: int) -> None:
@@ -225,15 +235,23 @@ def ivf_build_bytes(params: ivf_params, n: int) -> int:
     return int(out.value)
 
 
+def ivf_build_tmp_bytes(params: ivf_params, n: int, base_on_host: bool) -> int:
+    out = ctypes.c_size_t(0)
+    _check(_lib.ivf_build_tmp_bytes(ctypes.byref(params), n, int(base_on_host), ctypes.byref(out)), "ivf_build_tmp_bytes")
+    return int(out.value)
+
+
 def ivf_build(pool: int, params: ivf_params, base_ptr: int, n: int, centroids: Optional[np.ndarray],
-              dev_mem_ptr: int, dev_mem_bytes: int) -> int:
-    """base_ptr: host or device address of the row-major n x dim base (of params.dtype)."""
+              dev_mem_ptr: int, dev_mem_bytes: int, tmp_ptr: Optional[int] = None, tmp_bytes: int = 0) -> int:
+    """base_ptr: host or device address of the row-major n x dim base (of params.dtype).  tmp_ptr None: the
+    library allocates (and frees) its temporary device memory itself."""
     if centroids is not None:
         centroids = np.ascontiguousarray(centroids, dtype=np.float32)
         assert centroids.shape == (params.nlist, params.dim)
     out = ctypes.c_void_p(None)
     _check(_lib.ivf_build(ctypes.c_void_p(pool), ctypes.byref(params), ctypes.c_void_p(base_ptr), n,
-                          _np_ptr(centroids), ctypes.c_void_p(dev_mem_ptr), dev_mem_bytes, ctypes.byref(out)),
+                          _np_ptr(centroids), ctypes.c_void_p(dev_mem_ptr), dev_mem_bytes, ctypes.c_void_p(tmp_ptr), tmp_bytes,
+                          ctypes.byref(out)),
            "ivf_build")
     return out.value
 
@@ -441,8 +459,14 @@ def search_run_stream(pool: int, queries: np.ndarray, arrival_s: np.ndarray, str
 
 
 # ------------------------------------------------------------------------------------------- holders
+def _aligned(t, align=256):
+    return (t.data_ptr() + align - 1) // align * align
+
+
 class Pool:
-    """Owns the torch tensors that back a pool's device workspace and its indexes' storage."""
+    """Owns the torch tensors that back a pool: its device workspace, its pinned host memory and its
+    indexes' storage (the library allocates no device memory; library_memory=True lets it allocate
+    the pinned host memory and the temporary memory of index builds itself)."""
 
     def __init__(self, **cfg_fields):
         import torch
@@ -450,13 +474,18 @@ class Pool:
             raise RuntimeError("no GPU: the search path has no CPU fallback")
         # (a step can only be recorded for replay on a stream of its own, never on the default stream)
         own_stream = bool(cfg_fields.pop("own_stream", False))
+        self.library_memory = bool(cfg_fields.pop("library_memory", False))
         self.cfg = tri_pool_cfg(**cfg_fields)
         self._stream = torch.cuda.Stream() if own_stream or self.cfg.flags & TRI_FLAG_GRAPH else torch.cuda.current_stream()
         self.cfg.hip_stream = self._stream.cuda_stream
-        nbytes = tri_pool_workspace_bytes(self.cfg)
+        nbytes, pinned_bytes = tri_pool_workspace_bytes(self.cfg)
         self._ws = torch.empty(nbytes + 256, dtype=torch.uint8, device="cuda")
-        ptr = (self._ws.data_ptr() + 255) // 256 * 256
-        self.handle = tri_pool_create(self.cfg, ptr, nbytes)
+        self._pinned = None
+        if self.library_memory:
+            self.handle = tri_pool_create(self.cfg, _aligned(self._ws), nbytes)
+        else:
+            self._pinned = torch.empty(pinned_bytes + 256, dtype=torch.uint8, pin_memory=True)
+            self.handle = tri_pool_create(self.cfg, _aligned(self._ws), nbytes, _aligned(self._pinned), pinned_bytes)
         self._index_mem = {}
 
     def build_index(self, base, dim: int, nlist: int, dtype: int, build_metric: int, train_iters: int,
@@ -467,15 +496,20 @@ class Pool:
         n = int(base.shape[0])
         nbytes = ivf_build_bytes(params, n)
         mem = torch.empty(nbytes + 256, dtype=torch.uint8, device="cuda")
-        ptr = (mem.data_ptr() + 255) // 256 * 256
         if isinstance(base, np.ndarray):
             base = np.ascontiguousarray(base)
-            base_ptr = base.ctypes.data
+            base_ptr, on_host = base.ctypes.data, True
         else:
             base = base.contiguous()
-            base_ptr = base.data_ptr()
+            base_ptr, on_host = base.data_ptr(), not base.is_cuda
         torch.cuda.current_stream().synchronize()
-        index = ivf_build(self.handle, params, base_ptr, n, centroids, ptr, nbytes)
+        if self.library_memory:
+            index = ivf_build(self.handle, params, base_ptr, n, centroids, _aligned(mem), nbytes)
+        else:
+            tmp_bytes = ivf_build_tmp_bytes(params, n, on_host)
+            tmp = torch.empty(tmp_bytes + 256, dtype=torch.uint8, device="cuda")
+            index = ivf_build(self.handle, params, base_ptr, n, centroids, _aligned(mem), nbytes, _aligned(tmp), tmp_bytes)
+            del tmp
         self._index_mem[index] = mem
         return index
 
@@ -490,6 +524,7 @@ class Pool:
             tri_pool_destroy(self.handle)
             self.handle = None
             self._ws = None
+            self._pinned = None
 
     def __enter__(self):
         return self

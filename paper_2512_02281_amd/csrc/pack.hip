@@ -41,6 +41,27 @@ hipError_t tri_launch_fill_u32(hipStream_t s, uint32_t *p, uint32_t v, size_t n)
     return hipGetLastError();
 }
 
+// ---------------------------------------------------------------------------------------- stage
+// Rows of a caller's device array -> rows of the pool's own store (queries submitted with device-resident
+// vectors: from here on the caller's array is no longer needed).  One workgroup per row; the run a row
+// belongs to is found by walking the (short) run table, which arrives as a kernel argument.
+__global__ __launch_bounds__(256) void stage_rows_kernel(const TriStageRuns runs)
+{
+    uint32_t row = blockIdx.x, i = 0;
+    if (row >= runs.n_rows) return;
+    while (i + 1 < runs.n_runs && row >= runs.run[i].count) row -= runs.run[i++].count;
+    const uint16_t *src = (const uint16_t *)(runs.src + (uint64_t)(runs.run[i].src_first + row) * runs.src_pitch);
+    uint16_t *dst = (uint16_t *)(runs.dst + (uint64_t)(runs.run[i].dst_first + row) * runs.dst_pitch);
+    for (uint32_t e = threadIdx.x; e < runs.row_bytes / 2; e += 256) dst[e] = src[e];
+}
+
+hipError_t tri_launch_stage_rows(hipStream_t s, const TriStageRuns &runs)
+{
+    if (runs.n_rows == 0) return hipSuccess;
+    hipLaunchKernelGGL(stage_rows_kernel, dim3(runs.n_rows), dim3(256), 0, s, runs);
+    return hipGetLastError();
+}
+
 // ---------------------------------------------------------------------------------------- admit
 // One workgroup per admitted query: bring its zero-padded row into the slot -- from the pool's pinned
 // query store (host-submitted queries) or from the caller's device vector; either is also written to

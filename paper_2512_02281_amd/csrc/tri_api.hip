@@ -159,7 +159,11 @@ struct tri_pool {
     uint32_t n_running = 0;
     uint64_t admit_seq = 0, step_seq = 0;
     StepRec ring[RING];
-    uint8_t *pinned = nullptr;
+    uint8_t *pinned = nullptr;         // upload / result blocks of the steps in flight, then the query store
+    bool own_pinned = false;           // allocated here (hipHostMalloc) and freed in tri_pool_destroy
+    // a step that failed half-way leaves the slot table out of step with the GPU: the pool is then failed for good
+    bool failed = false, inject_failure = false;
+    std::string fail_text;
     tri_kernel_times times{};
     // scratch vectors reused by search_step
     std::vector<uint32_t> order, newq;
@@ -187,6 +191,7 @@ namespace {
 
 void drop_graphs(tri_pool *P);
 void feedback_tick(tri_pool *P);
+int step_locked(tri_pool *P, tri_step_stats *st);
 
 // Carve the device workspace.  Must match TriDevWs field for field.
 size_t carve(const tri_pool_cfg &c, uint32_t max_row_bytes, uint32_t coarse_rows, uint32_t coarse_ldc,
@@ -202,6 +207,7 @@ size_t carve(const tri_pool_cfg &c, uint32_t max_row_bytes, uint32_t coarse_rows
     uint8_t *p;
 #define CARVE(field, type, bytes) p = take(bytes); if (ws) ws->field = (type)p;
     CARVE(slot_query, uint8_t *, S * max_row_bytes)
+    CARVE(dev_qstore, uint8_t *, (size_t)c.max_outstanding * max_row_bytes)
     CARVE(slot_meta, TriSlotMeta *, S * sizeof(TriSlotMeta))
     CARVE(slot_qnorm, float *, S * 4)
     CARVE(probe, uint32_t *, S * c.nprobe_max * 4)
@@ -453,7 +459,30 @@ void enqueue_locked(tri_pool *P, const tri_query *q, tri_ticket *out)
 }  // namespace
 
 // ================================================================================== pool
-extern "C" int tri_pool_workspace_bytes(const tri_pool_cfg *cfg, size_t *dev_bytes)
+namespace {
+// Pinned host memory of a pool: RING x (upload block, result block), then the query store.
+struct PinnedLayout { size_t blk, prb, down_bytes, per_step, qstore_off, total; };
+
+PinnedLayout pinned_layout(const tri_pool_cfg &c, uint32_t max_row_bytes, size_t upload_bytes)
+{
+    PinnedLayout L;
+    const size_t S = c.slots;
+    L.blk = round_up_sz(S * (1 + 2 * (size_t)c.kmax) * 4, 256);
+    L.prb = round_up_sz(S * (size_t)c.nprobe_max * 4, 256);
+    L.down_bytes = L.blk + L.prb + 256;
+    L.per_step = round_up_sz(upload_bytes, 256) + L.down_bytes;
+    L.qstore_off = L.per_step * RING;
+    L.total = L.qstore_off + round_up_sz((size_t)c.max_outstanding * max_row_bytes, 256);
+    return L;
+}
+
+#define POOL_LIVE(P)                                                                                  \
+    do {                                                                                              \
+        if ((P)->failed) return tri_fail(TRI_EHIP, "the pool failed earlier: %s", (P)->fail_text.c_str()); \
+    } while (0)
+}  // namespace
+
+extern "C" int tri_pool_workspace_bytes(const tri_pool_cfg *cfg, size_t *dev_bytes, size_t *pinned_host_bytes)
 {
     uint32_t mrb, cr, ldc;
     uint64_t sc;
@@ -462,10 +491,12 @@ extern "C" int tri_pool_workspace_bytes(const tri_pool_cfg *cfg, size_t *dev_byt
     if (rc) return rc;
     if (!dev_bytes) return tri_fail(TRI_EINVAL, "dev_bytes is NULL");
     *dev_bytes = carve(*cfg, mrb, cr, ldc, sc, up, nullptr, nullptr);
+    if (pinned_host_bytes) *pinned_host_bytes = pinned_layout(*cfg, mrb, up).total;
     return TRI_OK;
 }
 
-extern "C" int tri_pool_create(const tri_pool_cfg *cfg, void *dev_ws, size_t dev_ws_bytes, tri_pool **out)
+extern "C" int tri_pool_create(const tri_pool_cfg *cfg, void *dev_ws, size_t dev_ws_bytes, void *pinned_ws,
+                               size_t pinned_ws_bytes, tri_pool **out)
 {
     uint32_t mrb, cr, ldc;
     uint64_t sc;
@@ -478,8 +509,20 @@ extern "C" int tri_pool_create(const tri_pool_cfg *cfg, void *dev_ws, size_t dev
     if ((uintptr_t)dev_ws % 256) return tri_fail(TRI_EINVAL, "dev_ws must be 256-byte aligned");
     const size_t need = carve(*cfg, mrb, cr, ldc, sc, up, nullptr, nullptr);
     if (dev_ws_bytes < need) return tri_fail(TRI_ENOMEM, "dev_ws has %zu bytes, %zu needed", dev_ws_bytes, need);
+    const PinnedLayout L = pinned_layout(*cfg, mrb, up);
+    if (pinned_ws) {
+        if ((uintptr_t)pinned_ws % 256) return tri_fail(TRI_EINVAL, "pinned_ws must be 256-byte aligned");
+        if (pinned_ws_bytes < L.total) return tri_fail(TRI_ENOMEM, "pinned_ws has %zu bytes, %zu needed", pinned_ws_bytes, L.total);
+    }
     int ndev = 0;
     if (hipGetDeviceCount(&ndev) != hipSuccess || ndev == 0) return tri_fail(TRI_EHIP, "no HIP device");
+    if (pinned_ws) {
+        void *as_dev = nullptr;                   // (page-locked and mapped, or not usable: the kernels read and write it)
+        if (hipHostGetDevicePointer(&as_dev, pinned_ws, 0) != hipSuccess || !as_dev) {
+            (void)hipGetLastError();
+            return tri_fail(TRI_EINVAL, "pinned_ws is not page-locked host memory the device can address");
+        }
+    }
     tri_pool *P = new (std::nothrow) tri_pool();
     if (!P) return tri_fail(TRI_ENOMEM, "out of host memory");
     P->cfg = *cfg;
@@ -492,22 +535,24 @@ extern "C" int tri_pool_create(const tri_pool_cfg *cfg, void *dev_ws, size_t dev
     carve(*cfg, mrb, cr, ldc, sc, up, (uint8_t *)dev_ws, &P->ws);
     P->ctx = TriLaunchCtx{P->stream, cfg->slots, cfg->items_per_step, cfg->kmax, cfg->nprobe_max,
                           cfg->max_total_lists, mrb, (uint32_t)prop.multiProcessorCount};
-    // pinned staging for RING steps
+    // pinned staging for RING steps and the query store: the caller's, or allocated here
     const size_t S = cfg->slots;
-    const size_t blk = round_up_sz(S * (1 + 2 * (size_t)cfg->kmax) * 4, 256);
-    const size_t prb = round_up_sz(S * (size_t)cfg->nprobe_max * 4, 256);
-    P->down_probe_off = blk;
-    P->down_step_off = blk + prb;
-    P->down_bytes = blk + prb + 256;
-    const size_t per = round_up_sz(up, 256) + P->down_bytes;
-    e = hipHostMalloc((void **)&P->pinned, per * RING, hipHostMallocDefault);
-    if (e != hipSuccess) { delete P; return tri_fail(TRI_EHIP, "hipHostMalloc(%zu) -> %s", per * RING, hipGetErrorString(e)); }
-    e = hipHostMalloc((void **)&P->qstore, (size_t)cfg->max_outstanding * mrb, hipHostMallocDefault);
-    if (e == hipSuccess) e = hipHostGetDevicePointer((void **)&P->qstore_dev, P->qstore, 0);
-    if (e != hipSuccess) { tri_pool_destroy(P); return tri_fail(TRI_EHIP, "hipHostMalloc(query store) -> %s", hipGetErrorString(e)); }
+    P->down_probe_off = L.blk;
+    P->down_step_off = L.blk + L.prb;
+    P->down_bytes = L.down_bytes;
+    if (pinned_ws) {
+        P->pinned = (uint8_t *)pinned_ws;
+    } else {
+        e = hipHostMalloc((void **)&P->pinned, L.total, hipHostMallocDefault);
+        if (e != hipSuccess) { delete P; return tri_fail(TRI_EHIP, "hipHostMalloc(%zu) -> %s", L.total, hipGetErrorString(e)); }
+        P->own_pinned = true;
+    }
+    P->qstore = P->pinned + L.qstore_off;
+    e = hipHostGetDevicePointer((void **)&P->qstore_dev, P->qstore, 0);
+    if (e != hipSuccess) { tri_pool_destroy(P); return tri_fail(TRI_EHIP, "hipHostGetDevicePointer(query store) -> %s", hipGetErrorString(e)); }
     for (uint32_t i = 0; i < RING; ++i) {
         StepRec &R = P->ring[i];
-        R.up_host = P->pinned + i * per;
+        R.up_host = P->pinned + i * L.per_step;
         R.down_host = R.up_host + round_up_sz(up, 256);
         e = hipHostGetDevicePointer((void **)&R.down_dev, R.down_host, 0);
         if (e == hipSuccess) e = hipHostGetDevicePointer((void **)&R.up_dev, R.up_host, 0);
@@ -548,8 +593,7 @@ extern "C" int tri_pool_destroy(tri_pool *P)
         for (uint32_t j = 0; j < N_EV; ++j)
             if (P->ring[i].ev[j]) (void)hipEventDestroy(P->ring[i].ev[j]);
     }
-    if (P->pinned) (void)hipHostFree(P->pinned);
-    if (P->qstore) (void)hipHostFree(P->qstore);
+    if (P->pinned && P->own_pinned) (void)hipHostFree(P->pinned);
     delete P;
     return TRI_OK;
 }
@@ -576,16 +620,57 @@ extern "C" int ivf_build_bytes(const ivf_params *p, uint64_t n, size_t *dev_byte
 }
 
 namespace {
-struct TmpMem {      // frees its device allocations on scope exit
+// Temporary device memory of a build: carved from the caller's scratch, or -- without one -- allocated
+// piece by piece and freed on scope exit.
+struct TmpMem {
+    uint8_t *arena = nullptr;
+    size_t arena_bytes = 0, used = 0;
     std::vector<void *> ptrs;
     ~TmpMem() { for (void *p : ptrs) (void)hipFree(p); }
     hipError_t alloc(void **p, size_t bytes)
     {
-        hipError_t e = hipMalloc(p, bytes ? bytes : 256);
+        bytes = round_up_sz(bytes ? bytes : 256, 256);
+        if (arena) {
+            if (used + bytes > arena_bytes) return hipErrorOutOfMemory;
+            *p = arena + used;
+            used += bytes;
+            return hipSuccess;
+        }
+        hipError_t e = hipMalloc(p, bytes);
         if (e == hipSuccess) ptrs.push_back(*p);
         return e;
     }
 };
+
+// Sizes of a build's temporary buffers (what ivf_build asks TmpMem for, in that order).
+struct BuildTmp {
+    uint32_t ldc, chunk, nblocks;
+    uint64_t ns;
+    size_t base_copy, cent_f32, scores, chunk_rows, assign, block_hist, list_len, train, perm_s, loff_s, total;
+};
+
+BuildTmp build_tmp(const ivf_params &p, uint64_t n, bool base_on_host)
+{
+    BuildTmp t{};
+    const uint32_t es = esize(p.dtype), dpad = dpad_of(p.dim, p.dtype), rb = dpad * es;
+    t.ldc = round_up(p.nlist, 32);
+    t.chunk = round_up((uint32_t)std::min<uint64_t>(n, std::max<uint64_t>(128, (256ull << 20) / t.ldc)), 128);
+    t.nblocks = (uint32_t)std::min<uint64_t>(512, (n + 255) / 256);
+    t.ns = p.train_iters ? (n <= 256ull * p.nlist ? n : 256ull * p.nlist) : 0;
+    t.base_copy = base_on_host ? (size_t)n * p.dim * es : 0;
+    t.cent_f32 = (size_t)p.nlist * dpad * 4;
+    t.scores = (size_t)t.chunk * t.ldc * 4;
+    t.chunk_rows = (size_t)t.chunk * rb;
+    t.assign = (size_t)n * 4;
+    t.block_hist = (size_t)t.nblocks * p.nlist * 4;
+    t.list_len = (size_t)p.nlist * 4;
+    t.train = (size_t)t.ns * rb;
+    t.perm_s = (size_t)t.ns * 4;
+    t.loff_s = t.ns ? ((size_t)p.nlist + 1) * 4 : 0;
+    for (size_t b : {t.base_copy, t.cent_f32, t.scores, t.chunk_rows, t.assign, t.block_hist, t.list_len, t.train, t.perm_s, t.loff_s})
+        if (b) t.total += round_up_sz(b, 256);
+    return t;
+}
 
 uint64_t splitmix64(uint64_t &s)
 {
@@ -618,17 +703,29 @@ int assign_all(hipStream_t s, int dtype, uint32_t dim, uint32_t dpad, uint32_t r
 }
 }  // namespace
 
+extern "C" int ivf_build_tmp_bytes(const ivf_params *p, uint64_t n, int base_on_host, size_t *tmp_bytes)
+{
+    size_t unused = 0;
+    int rc = ivf_build_bytes(p, n, &unused);        // (validates the parameters)
+    if (rc) return rc;
+    if (!tmp_bytes) return tri_fail(TRI_EINVAL, "tmp_bytes is NULL");
+    *tmp_bytes = build_tmp(*p, n, base_on_host != 0).total;
+    return TRI_OK;
+}
+
 extern "C" int ivf_build(tri_pool *P, const ivf_params *p, const void *base, uint64_t n, const float *centroids,
-                         void *dev_mem, size_t dev_mem_bytes, tri_index **out)
+                         void *dev_mem, size_t dev_mem_bytes, void *tmp_dev, size_t tmp_bytes, tri_index **out)
 {
     if (!P || !p || !base || !dev_mem || !out) return tri_fail(TRI_EINVAL, "NULL argument");
     size_t need = 0;
     int rc = ivf_build_bytes(p, n, &need);
     if (rc) return rc;
+    if (tmp_dev && (uintptr_t)tmp_dev % 256) return tri_fail(TRI_EINVAL, "tmp_dev must be 256-byte aligned");
     if (p->build_metric != TRI_L2 && p->build_metric != TRI_IP) return tri_fail(TRI_EINVAL, "build_metric must be TRI_L2 or TRI_IP");
     if ((uintptr_t)dev_mem % 256) return tri_fail(TRI_EINVAL, "dev_mem must be 256-byte aligned");
     if (dev_mem_bytes < need) return tri_fail(TRI_ENOMEM, "dev_mem has %zu bytes, %zu needed", dev_mem_bytes, need);
     std::lock_guard<std::mutex> lk(P->mu);
+    POOL_LIVE(P);
     if (p->dim > P->cfg.max_dim) return tri_fail(TRI_EINVAL, "dim %u > pool max_dim %u", p->dim, P->cfg.max_dim);
     if (p->nlist > P->cfg.max_nlist) return tri_fail(TRI_EINVAL, "nlist %u > pool max_nlist %u", p->nlist, P->cfg.max_nlist);
     if ((uint64_t)P->total_lists + p->nlist > P->cfg.max_total_lists)
@@ -658,7 +755,6 @@ extern "C" int ivf_build(tri_pool *P, const ivf_params *p, const void *base, uin
     uint8_t *cent = m;              m += round_up_sz((size_t)nlist * rb, 256);
     float *cnorm = (float *)m;
 
-    TmpMem tmp;
     // base on the device
     const void *dbase = base;
     hipPointerAttribute_t attr;
@@ -667,27 +763,31 @@ extern "C" int ivf_build(tri_pool *P, const ivf_params *p, const void *base, uin
         on_device = attr.type == hipMemoryTypeDevice || attr.type == hipMemoryTypeManaged;
     else
         (void)hipGetLastError();     // plain host memory: the query itself reports an error
+    const BuildTmp bt = build_tmp(*p, n, !on_device);
+    TmpMem tmp;
+    if (tmp_dev) {
+        if (tmp_bytes < bt.total) return tri_fail(TRI_ENOMEM, "tmp_dev has %zu bytes, %zu needed", tmp_bytes, bt.total);
+        tmp.arena = (uint8_t *)tmp_dev;
+        tmp.arena_bytes = tmp_bytes;
+    }
     if (!on_device) {
         void *d = nullptr;
-        HIP_TRY(tmp.alloc(&d, (size_t)n * dim * es));
+        HIP_TRY(tmp.alloc(&d, bt.base_copy));
         HIP_TRY(hipMemcpy(d, base, (size_t)n * dim * es, hipMemcpyHostToDevice));
         dbase = d;
     }
     // working buffers
     float *cent_f32 = nullptr;
-    HIP_TRY(tmp.alloc((void **)&cent_f32, (size_t)nlist * dpad * 4));
-    const uint32_t ldc = round_up(nlist, 32);
-    uint32_t chunk = (uint32_t)std::min<uint64_t>(n, std::max<uint64_t>(128, (256ull << 20) / ldc));
-    chunk = round_up(chunk, 128);
+    HIP_TRY(tmp.alloc((void **)&cent_f32, bt.cent_f32));
+    const uint32_t ldc = bt.ldc, chunk = bt.chunk, nblocks = bt.nblocks;
     float *scores = nullptr;
     void *chunk_rows = nullptr;
     uint32_t *assign = nullptr, *block_hist = nullptr, *list_len = nullptr;
-    HIP_TRY(tmp.alloc((void **)&scores, (size_t)chunk * ldc * 4));
-    HIP_TRY(tmp.alloc(&chunk_rows, (size_t)chunk * rb));
-    HIP_TRY(tmp.alloc((void **)&assign, (size_t)n * 4));
-    const uint32_t nblocks = (uint32_t)std::min<uint64_t>(512, (n + 255) / 256);
-    HIP_TRY(tmp.alloc((void **)&block_hist, (size_t)nblocks * nlist * 4));
-    HIP_TRY(tmp.alloc((void **)&list_len, (size_t)nlist * 4));
+    HIP_TRY(tmp.alloc((void **)&scores, bt.scores));
+    HIP_TRY(tmp.alloc(&chunk_rows, bt.chunk_rows));
+    HIP_TRY(tmp.alloc((void **)&assign, bt.assign));
+    HIP_TRY(tmp.alloc((void **)&block_hist, bt.block_hist));
+    HIP_TRY(tmp.alloc((void **)&list_len, bt.list_len));
 
     // ---- initial centroids
     if (centroids) {
@@ -705,12 +805,12 @@ extern "C" int ivf_build(tri_pool *P, const ivf_params *p, const void *base, uin
 
     // ---- Lloyd iterations on the training rows
     if (p->train_iters) {
-        const uint64_t ns = n <= 256ull * nlist ? n : 256ull * nlist;
+        const uint64_t ns = bt.ns;
         void *train = nullptr;
         uint32_t *perm_s = nullptr, *loff_s = nullptr;
-        HIP_TRY(tmp.alloc(&train, (size_t)ns * rb));
-        HIP_TRY(tmp.alloc((void **)&perm_s, (size_t)ns * 4));
-        HIP_TRY(tmp.alloc((void **)&loff_s, ((size_t)nlist + 1) * 4));
+        HIP_TRY(tmp.alloc(&train, bt.train));
+        HIP_TRY(tmp.alloc((void **)&perm_s, bt.perm_s));
+        HIP_TRY(tmp.alloc((void **)&loff_s, bt.loff_s));
         uint64_t a = 1, b = 0;
         if (ns < n) {
             uint64_t st = p->seed ^ 0x7472696e69747921ull;
@@ -828,11 +928,15 @@ extern "C" int ivf_destroy(tri_index *ix)
     if (!ix) return tri_fail(TRI_EINVAL, "index is NULL");
     tri_pool *P = ix->pool;
     std::lock_guard<std::mutex> lk(P->mu);
-    if (P->n_running || !P->pending[0].empty() || !P->pending[1].empty())
-        return tri_fail(TRI_EINVAL, "ivf_destroy while queries are queued or running");
-    int rc = reap(P, true, nullptr);
-    if (rc) return rc;
-    HIP_TRY(hipStreamSynchronize(P->stream));
+    if (!P->failed) {
+        if (P->n_running || !P->pending[0].empty() || !P->pending[1].empty())
+            return tri_fail(TRI_EINVAL, "ivf_destroy while queries are queued or running");
+        int rc = reap(P, true, nullptr);
+        if (rc) return rc;
+        HIP_TRY(hipStreamSynchronize(P->stream));
+    } else {
+        (void)hipStreamSynchronize(P->stream);      // (a failed pool is only torn down)
+    }
     // finished, unpolled tickets of this index stay valid: their results are already on the host
     P->indexes[ix->id] = nullptr;
     P->attached_row_bytes = 128;
@@ -845,7 +949,7 @@ extern "C" int ivf_destroy(tri_index *ix)
     if (ix->list_base + ix->p.nlist == P->total_lists) P->total_lists = ix->list_base;   // last attached: give its list range back
     delete ix;
     drop_graphs(P);
-    return upload_scan_order(P);
+    return P->failed ? TRI_OK : upload_scan_order(P);
 }
 
 // ================================================================================== search
@@ -854,6 +958,7 @@ extern "C" int search_submit_batch(tri_pool *P, const tri_query *q, uint32_t n, 
     if (n_done) *n_done = 0;
     if (!P || (!q && n) || (!out && n)) return tri_fail(TRI_EINVAL, "NULL argument");
     std::lock_guard<std::mutex> lk(P->mu);
+    POOL_LIVE(P);
     const tri_index *known = nullptr;
     for (uint32_t i = 0; i < n; ++i) {
         int rc = validate_query(P, &q[i], &known);
@@ -876,6 +981,7 @@ extern "C" int search_submit_batch_dev(tri_pool *P, const tri_index *index, cons
     if (n_done) *n_done = 0;
     if (!P || !index || (n && (!vecs || !k || !nprobe || !metric || !klass || !out))) return tri_fail(TRI_EINVAL, "NULL argument");
     std::lock_guard<std::mutex> lk(P->mu);
+    POOL_LIVE(P);
     if (!is_attached(P, index)) return tri_fail(TRI_EINVAL, "index is not attached to this pool");
     const uint32_t es = esize(index->p.dtype);
     if (pitch_bytes % es || pitch_bytes < (uint64_t)index->p.dim * es || (uintptr_t)vecs % es)
@@ -889,10 +995,33 @@ extern "C" int search_submit_batch_dev(tri_pool *P, const tri_index *index, cons
         int rc = validate_query(P, &q, &known);
         if (rc) return rc;
     }
-    for (uint32_t i = 0; i < n; ++i) {
-        if (P->free_tickets.empty()) return tri_fail(TRI_EAGAIN, "max_outstanding=%u tickets alive", P->cfg.max_outstanding);
-        const uint32_t ti = P->free_tickets.back();
-        P->free_tickets.pop_back();
+    // tickets for as many as there is room for, in ascending order: query i's row then goes to store row
+    // ticket[i], and stretches of consecutive tickets are copied as runs by one kernel of the pool's stream
+    const uint32_t m = (uint32_t)std::min<size_t>(n, P->free_tickets.size());
+    std::vector<uint32_t> tk(P->free_tickets.end() - m, P->free_tickets.end());
+    std::sort(tk.begin(), tk.end());
+    if (m) {
+        HIP_TRY(hipSetDevice(P->device));
+        TriStageRuns runs{};
+        runs.src = (uint64_t)(uintptr_t)vecs; runs.src_pitch = pitch_bytes;
+        runs.dst = (uint64_t)(uintptr_t)P->ws.dev_qstore; runs.dst_pitch = P->max_row_bytes;
+        runs.row_bytes = index->p.dim * es;
+        for (uint32_t i = 0; i < m;) {
+            uint32_t j = i + 1;
+            while (j < m && tk[j] == tk[j - 1] + 1) ++j;
+            runs.run[runs.n_runs].src_first = i; runs.run[runs.n_runs].dst_first = tk[i]; runs.run[runs.n_runs].count = j - i;
+            ++runs.n_runs;
+            runs.n_rows += j - i;
+            if (runs.n_runs == TRI_STAGE_RUNS || j == m) {
+                HIP_TRY(tri_launch_stage_rows(P->stream, runs));      // (nothing has been queued yet: the tickets are still free)
+                runs.n_runs = runs.n_rows = 0;
+            }
+            i = j;
+        }
+    }
+    P->free_tickets.resize(P->free_tickets.size() - m);
+    for (uint32_t i = 0; i < m; ++i) {
+        const uint32_t ti = tk[i];
         Ticket &t = P->tickets[ti];
         t.state = T_PENDING;
         t.cancelled = false;
@@ -901,11 +1030,12 @@ extern "C" int search_submit_batch_dev(tri_pool *P, const tri_index *index, cons
         t.tag = 0;
         t.submit_ns = now_ns();
         t.deadline_ns = INT64_MAX;
-        t.dev_vec = (const uint8_t *)vecs + (size_t)i * pitch_bytes;
+        t.dev_vec = P->ws.dev_qstore + (size_t)ti * P->max_row_bytes;
         P->pending[t.klass].push_back(ti);
         out[i] = ((uint64_t)t.gen << 32) | ti;
-        if (n_done) *n_done = i + 1;
     }
+    if (n_done) *n_done = m;
+    if (m < n) return tri_fail(TRI_EAGAIN, "max_outstanding=%u tickets alive", P->cfg.max_outstanding);
     return TRI_OK;
 }
 
@@ -1027,6 +1157,18 @@ extern "C" int search_step(tri_pool *P, tri_step_stats *st)
 {
     if (!P) return tri_fail(TRI_EINVAL, "pool is NULL");
     std::lock_guard<std::mutex> lk(P->mu);
+    POOL_LIVE(P);
+    const int rc_step = step_locked(P, st);
+    if (rc_step == TRI_EHIP) {          // queries may have been admitted on the host that the GPU never saw
+        P->failed = true;
+        P->fail_text = g_err;
+    }
+    return rc_step;
+}
+
+namespace {
+int step_locked(tri_pool *P, tri_step_stats *st)
+{
     HIP_TRY(hipSetDevice(P->device));
     tri_step_stats stats{};
     int rc = reap(P, false, &stats.finished);
@@ -1191,6 +1333,10 @@ extern "C" int search_step(tri_pool *P, tri_step_stats *st)
     }
     hdr_h->n_groups = n_groups;
 
+    if (P->inject_failure) {
+        P->inject_failure = false;
+        return tri_fail(TRI_EHIP, "injected failure (tri_pool_inject_failure)");
+    }
     hipStream_t s = P->stream;
     const bool prof = (cfg.flags & TRI_FLAG_PROFILE) != 0;
     const bool prof_scan = !prof && (cfg.flags & TRI_FLAG_PROFILE_SCAN) != 0;
@@ -1267,6 +1413,7 @@ extern "C" int search_step(tri_pool *P, tri_step_stats *st)
     if (st) *st = stats;
     return TRI_OK;
 }
+}  // namespace
 
 namespace {
 // search_poll without the lock and without the reap; returns TRI_OK / TRI_EAGAIN / TRI_ENOENT / TRI_EINVAL
@@ -1298,6 +1445,7 @@ extern "C" int search_poll(tri_pool *P, tri_ticket tk, uint32_t *n_out, int64_t 
 {
     if (!P) return tri_fail(TRI_EINVAL, "pool is NULL");
     std::lock_guard<std::mutex> lk(P->mu);
+    POOL_LIVE(P);
     HIP_TRY(hipSetDevice(P->device));
     int rc = reap(P, false, nullptr);
     if (rc) return rc;
@@ -1309,6 +1457,7 @@ extern "C" int search_poll_batch(tri_pool *P, const tri_ticket *tk, uint32_t n, 
 {
     if (!P || (n && (!tk || !ids || !dist || !status || !n_out))) return tri_fail(TRI_EINVAL, "NULL argument");
     std::lock_guard<std::mutex> lk(P->mu);
+    POOL_LIVE(P);
     HIP_TRY(hipSetDevice(P->device));
     int rc = reap(P, false, nullptr);
     if (rc) return rc;
@@ -1368,6 +1517,7 @@ extern "C" int search_sync(tri_pool *P)
 {
     if (!P) return tri_fail(TRI_EINVAL, "pool is NULL");
     std::lock_guard<std::mutex> lk(P->mu);
+    POOL_LIVE(P);
     HIP_TRY(hipSetDevice(P->device));
     return reap(P, true, nullptr);
 }
@@ -1491,6 +1641,7 @@ extern "C" int search_run_stream(tri_pool *P, const tri_query *q, const double *
         return tri_fail(TRI_EINVAL, "probe lists need a pool created with TRI_FLAG_KEEP_PROBES");
     {
         std::lock_guard<std::mutex> lk(P->mu);
+        POOL_LIVE(P);
         if (P->free_tickets.size() != P->tickets.size()) return tri_fail(TRI_EINVAL, "the pool has queries in flight");
         const tri_index *known = nullptr;
         for (uint32_t i = 0; i < n; ++i) {
@@ -1605,6 +1756,14 @@ extern "C" int tri_pool_set_replay(tri_pool *P, int on)
     if (on && !P->stream) return tri_fail(TRI_EINVAL, "a step cannot be recorded on the default stream: give the pool a stream of its own");
     std::lock_guard<std::mutex> lk(P->mu);
     P->cfg.flags = on ? (P->cfg.flags | TRI_FLAG_GRAPH) : (P->cfg.flags & ~(uint32_t)TRI_FLAG_GRAPH);
+    return TRI_OK;
+}
+
+extern "C" int tri_pool_inject_failure(tri_pool *P)
+{
+    if (!P) return tri_fail(TRI_EINVAL, "pool is NULL");
+    std::lock_guard<std::mutex> lk(P->mu);
+    P->inject_failure = true;
     return TRI_OK;
 }
 

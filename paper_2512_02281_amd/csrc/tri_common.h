@@ -129,6 +129,7 @@ struct TriStepDev {
 struct TriDevWs {
     // persistent per-slot state
     uint8_t *slot_query;      // [S][slot_row_bytes]
+    uint8_t *dev_qstore;      // [max_outstanding][slot_row_bytes] rows of device-submitted queries, by ticket number
     TriSlotMeta *slot_meta;   // [S]
     float *slot_qnorm;        // [S]
     uint32_t *probe;          // [S][nprobe_max]
@@ -188,6 +189,15 @@ int tri_fail(int code, const char *fmt, ...) __attribute__((format(printf, 2, 3)
 hipError_t tri_launch_fill_u32(hipStream_t s, uint32_t *p, uint32_t v, size_t n);
 hipError_t tri_launch_pull_block(hipStream_t s, void *dst_dev, const void *src_host_as_device, size_t grid_bytes);
 hipError_t tri_launch_admit(const TriLaunchCtx &c, const TriDevWs &ws, uint32_t grid_new);
+// Copy rows of a caller's device array into rows of the pool's store: run i moves `count` consecutive source
+// rows starting at src_first to consecutive store rows starting at dst_first (row_bytes bytes each, a multiple of 2).
+#define TRI_STAGE_RUNS 120
+struct TriStageRuns {
+    uint64_t src, src_pitch, dst, dst_pitch;
+    uint32_t row_bytes, n_runs, n_rows, pad_;
+    struct { uint32_t src_first, dst_first, count; } run[TRI_STAGE_RUNS];
+};
+hipError_t tri_launch_stage_rows(hipStream_t s, const TriStageRuns &runs);
 // scores[m][ldc] for m rows (pitch a_pitch_bytes) against n rows of b (pitch row_bytes); the metric
 // is per row (row_metric[m * metric_stride_u32]) or, with row_metric == NULL, fixed_metric.
 hipError_t tri_launch_coarse_gemm(hipStream_t s, int dtype, const void *a_rows, uint32_t a_pitch_bytes,

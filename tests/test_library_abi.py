@@ -82,11 +82,15 @@ def _cfg(tri, **over):
 
 
 def test_workspace_size_and_config_validation(tri):
-    small = tri.tri_pool_workspace_bytes(_cfg(tri))
-    big = tri.tri_pool_workspace_bytes(_cfg(tri, slots=4096, items_per_step=1 << 18, max_outstanding=8192))
+    small, small_pinned = tri.tri_pool_workspace_bytes(_cfg(tri))
+    big, big_pinned = tri.tri_pool_workspace_bytes(_cfg(tri, slots=4096, items_per_step=1 << 18, max_outstanding=8192))
     assert 0 < small < big and small % 256 == 0
     # the score buffer dominates: W * 1024 floats by default
     assert big > (1 << 18) * 1024 * 4
+    # pinned host memory: result blocks of the four steps that may be in flight (ids and scores of every slot's
+    # kmax results) and a padded row (fp32 rows of max_dim are the widest) per outstanding ticket
+    assert small_pinned % 256 == 0 and small_pinned >= 4 * 64 * 2 * 100 * 4 + 256 * 768 * 4
+    assert big_pinned >= 4 * 4096 * 2 * 100 * 4 + 8192 * 768 * 4 and big_pinned < 2 * (4 * 4096 * 2 * 100 * 4 + 8192 * 768 * 4) + (64 << 20)
     for bad in (dict(slots=0), dict(items_per_step=0), dict(kmax=0), dict(kmax=2000), dict(nprobe_max=0),
                 dict(nprobe_max=5000), dict(max_indexes=0), dict(max_nlist=0), dict(max_total_lists=10),
                 dict(max_dim=0), dict(max_dim=4096), dict(max_outstanding=8)):
@@ -103,12 +107,22 @@ def test_index_size_and_parameter_validation(tri):
     assert got < n * 768 * 2 * 1.02 + (1 << 20)
     p32 = tri.ivf_params(100, 16, tri.TRI_F32, tri.TRI_L2, 0, 0)   # dim 100 fp32 pads to 128 elements
     assert tri.ivf_build_bytes(p32, 1000) >= 1000 * 128 * 4
+    # temporary memory of a build: a padded copy of the training rows dominates (all rows when n <= 256 nlist),
+    # a host-resident base adds its device copy, no training leaves the score block and the assignment tables
+    t_dev = tri.ivf_build_tmp_bytes(p, n, False)
+    t_host = tri.ivf_build_tmp_bytes(p, n, True)
+    p0 = tri.ivf_params(768, 1024, tri.TRI_F16, tri.TRI_IP, 0, 1)
+    assert t_dev % 256 == 0 and t_dev >= n * 768 * 2 + n * 4 and 0 <= t_host - t_dev - n * 768 * 2 < 512
+    assert tri.ivf_build_tmp_bytes(p0, n, False) <= t_dev - n * 768 * 2
     for bad, nn in ((tri.ivf_params(0, 4, 0, 0, 0, 0), 10), (tri.ivf_params(8, 0, 0, 0, 0, 0), 10),
                     (tri.ivf_params(8, 4, 7, 0, 0, 0), 10), (tri.ivf_params(8, 4, 0, 0, 0, 0), 0),
                     (tri.ivf_params(8, 40, 0, 0, 0, 0), 10), (tri.ivf_params(5000, 4, 1, 0, 0, 0), 10),
                     (tri.ivf_params(8, 4, 0, 0, 0, 0), 1 << 33)):
         with pytest.raises(tri.TriError) as ei:
             tri.ivf_build_bytes(bad, nn)
+        assert ei.value.status == tri.TRI_EINVAL
+        with pytest.raises(tri.TriError) as ei:
+            tri.ivf_build_tmp_bytes(bad, nn, False)
         assert ei.value.status == tri.TRI_EINVAL
 
 
