@@ -10,6 +10,8 @@ if ROOT not in sys.path:
 
 def pytest_configure(config):
     config.addinivalue_line("markers", "gpu: needs a real MI355X (run with -m gpu)")
+    from tests import harness
+    harness.PYTEST_CONFIG = config          # lets harness.say() write progress lines past pytest's capture
 
 
 def pytest_collection_modifyitems(config, items):

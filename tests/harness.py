@@ -9,6 +9,20 @@ from oracle import index as oindex
 from tests import checker
 
 
+PYTEST_CONFIG = None     # set by conftest.py
+
+
+def say(msg):
+    """A progress line that reaches the terminal (and the log of whoever runs the tests) even for a passing
+    test: names the case before each long GPU step and carries the parity reports."""
+    capman = PYTEST_CONFIG.pluginmanager.get_plugin("capturemanager") if PYTEST_CONFIG is not None else None
+    if capman is None:
+        print(msg, flush=True)
+        return
+    with capman.global_and_fixture_disabled():
+        print(f"\n    {msg}", end="", flush=True)
+
+
 def lib():
     import paper_2512_02281_amd as tri
     return tri

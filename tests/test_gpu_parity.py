@@ -16,7 +16,7 @@ GOLDEN = os.path.join(os.path.dirname(__file__), "golden", "worked_examples.json
 
 
 def _say(msg):
-    print(msg, flush=True)
+    harness.say(msg)
 
 
 @pytest.mark.parametrize("dtype", ["f32", "f16"])
