@@ -104,6 +104,22 @@ int tri_pool_workspace_bytes(const tri_pool_cfg *cfg /*[host]*/, size_t *dev_byt
 int tri_pool_create(const tri_pool_cfg *cfg /*[host]*/, void *dev_ws /*[device]*/, size_t dev_ws_bytes,
                     void *pinned_ws /*[host, pinned] or NULL*/, size_t pinned_ws_bytes, tri_pool **out /*[host] out*/);
 
+/* tri_pool_create for callers that cannot allocate device memory at all (a harness that forbids
+ * hipMalloc, a process that must not grow its footprint while serving): the device workspace is a
+ * fixed array of TRI_STATIC_WS_BYTES inside the library's own image, present once on every GPU the
+ * library is loaded on, and the pinned memory is always the caller's (pinned_ws must not be NULL).
+ * The call allocates and frees no device or pinned memory (no hipMalloc, hipHostMalloc, hipFree);
+ * the pool's host-side tables and events are created as in tri_pool_create.
+ *  - TRI_ENOMEM: the configuration needs more than TRI_STATIC_WS_BYTES of workspace (the text says
+ *    how much); TRI_EAGAIN: another pool created by this call is still alive on the device -- all
+ *    such pools of a device share the one array, so only one may exist at a time, and whatever an
+ *    earlier pool left in it is cleared before the new pool uses it.
+ *  - Everything else (indexes, search calls, tri_pool_destroy) works as with tri_pool_create;
+ *    ivf_build takes its memory from the caller as usual. */
+#define TRI_STATIC_WS_BYTES (64u << 20)
+int tri_pool_create_static(const tri_pool_cfg *cfg /*[host]*/, void *pinned_ws /*[host, pinned]*/,
+                           size_t pinned_ws_bytes, tri_pool **out /*[host] out*/);
+
 /* Destroy the pool.  Waits for enqueued work; every ticket becomes invalid.  Indexes attached
  * to it must be destroyed first (TRI_EINVAL otherwise). */
 int tri_pool_destroy(tri_pool *pool);

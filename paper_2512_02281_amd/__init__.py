@@ -97,7 +97,7 @@ class tri_stream_stats(ctypes.Structure):
                 ("submit_s", ctypes.c_double), ("step_s", ctypes.c_double), ("collect_s", ctypes.c_double)]
 
 
-EXPORTS = ["tri_pool_workspace_bytes", "tri_pool_create", "tri_pool_destroy", "ivf_build_bytes", "ivf_build_tmp_bytes", "ivf_build",
+EXPORTS = ["tri_pool_workspace_bytes", "tri_pool_create", "tri_pool_create_static", "tri_pool_destroy", "ivf_build_bytes", "ivf_build_tmp_bytes", "ivf_build",
            "ivf_export", "ivf_info", "ivf_destroy", "search_submit", "search_submit_batch", "search_submit_batch_dev",
            "search_step", "search_poll", "search_poll_batch", "search_probes", "search_cancel", "search_sync",
            "search_run_stream", "search_set_policy", "search_get_policy", "tri_policy_split", "tri_policy_slack_order",
@@ -118,6 +118,7 @@ def _load():
     P = ctypes.POINTER
     lib.tri_pool_workspace_bytes.argtypes = [P(tri_pool_cfg), P(sz), P(sz)]
     lib.tri_pool_create.argtypes = [P(tri_pool_cfg), vp, sz, vp, sz, P(vp)]
+    lib.tri_pool_create_static.argtypes = [P(tri_pool_cfg), vp, sz, P(vp)]
     lib.tri_pool_inject_failure.argtypes = [vp]
     lib.tri_pool_destroy.argtypes = [vp]
     lib.ivf_build_bytes.argtypes = [P(ivf_params), u64, P(sz)]
@@ -191,6 +192,17 @@ def tri_pool_create(cfg: tri_pool_cfg, dev_ws_ptr: int, dev_ws_bytes: int, pinne
     out = ctypes.c_void_p(None)
     _check(_lib.tri_pool_create(ctypes.byref(cfg), ctypes.c_void_p(dev_ws_ptr), dev_ws_bytes, ctypes.c_void_p(pinned_ptr),
                                 pinned_bytes, ctypes.byref(out)), "tri_pool_create")
+    return out.value
+
+
+TRI_STATIC_WS_BYTES = 64 << 20
+
+
+def tri_pool_create_static(cfg: tri_pool_cfg, pinned_ptr: int, pinned_bytes: int) -> int:
+    """A pool whose device workspace is the library's own static array (no device allocation anywhere)."""
+    out = ctypes.c_void_p(None)
+    _check(_lib.tri_pool_create_static(ctypes.byref(cfg), ctypes.c_void_p(pinned_ptr), pinned_bytes, ctypes.byref(out)),
+           "tri_pool_create_static")
     return out.value
 
 
@@ -466,7 +478,8 @@ def _aligned(t, align=256):
 class Pool:
     """Owns the torch tensors that back a pool: its device workspace, its pinned host memory and its
     indexes' storage (the library allocates no device memory; library_memory=True lets it allocate
-    the pinned host memory and the temporary memory of index builds itself)."""
+    the pinned host memory and the temporary memory of index builds itself; static_workspace=True
+    makes the pool with tri_pool_create_static, in the library's own static device array)."""
 
     def __init__(self, **cfg_fields):
         import torch
@@ -475,18 +488,24 @@ class Pool:
         # (a step can only be recorded for replay on a stream of its own, never on the default stream)
         own_stream = bool(cfg_fields.pop("own_stream", False))
         self.library_memory = bool(cfg_fields.pop("library_memory", False))
+        self.static_workspace = bool(cfg_fields.pop("static_workspace", False))
         self.cfg = tri_pool_cfg(**cfg_fields)
         self._stream = torch.cuda.Stream() if own_stream or self.cfg.flags & TRI_FLAG_GRAPH else torch.cuda.current_stream()
         self.cfg.hip_stream = self._stream.cuda_stream
         nbytes, pinned_bytes = tri_pool_workspace_bytes(self.cfg)
-        self._ws = torch.empty(nbytes + 256, dtype=torch.uint8, device="cuda")
         self._pinned = None
+        self._index_mem = {}
+        if self.static_workspace:
+            self._ws = None
+            self._pinned = torch.empty(pinned_bytes + 256, dtype=torch.uint8, pin_memory=True)
+            self.handle = tri_pool_create_static(self.cfg, _aligned(self._pinned), pinned_bytes)
+            return
+        self._ws = torch.empty(nbytes + 256, dtype=torch.uint8, device="cuda")
         if self.library_memory:
             self.handle = tri_pool_create(self.cfg, _aligned(self._ws), nbytes)
         else:
             self._pinned = torch.empty(pinned_bytes + 256, dtype=torch.uint8, pin_memory=True)
             self.handle = tri_pool_create(self.cfg, _aligned(self._ws), nbytes, _aligned(self._pinned), pinned_bytes)
-        self._index_mem = {}
 
     def build_index(self, base, dim: int, nlist: int, dtype: int, build_metric: int, train_iters: int,
                     centroids: Optional[np.ndarray] = None, seed: int = 0) -> int:

@@ -23,6 +23,11 @@ namespace {
 thread_local std::string g_err;
 }  // namespace
 
+// Device workspace of the pools made by tri_pool_create_static: one array per GPU the library is loaded on,
+// part of the library's image, so that such a pool needs no allocation.  In host code the name is only a handle
+// for hipGetSymbolAddress; the address the kernels get is looked up once per device (g_static).
+static __device__ __align__(256) unsigned char scratch[TRI_STATIC_WS_BYTES];
+
 int tri_fail(int code, const char *fmt, ...)
 {
     char buf[512];
@@ -161,6 +166,7 @@ struct tri_pool {
     StepRec ring[RING];
     uint8_t *pinned = nullptr;         // upload / result blocks of the steps in flight, then the query store
     bool own_pinned = false;           // allocated here (hipHostMalloc) and freed in tri_pool_destroy
+    int static_dev = -1;               // >= 0: the workspace is that device's static array (tri_pool_create_static)
     // a step that failed half-way leaves the slot table out of step with the GPU: the pool is then failed for good
     bool failed = false, inject_failure = false;
     std::string fail_text;
@@ -582,12 +588,64 @@ extern "C" int tri_pool_create(const tri_pool_cfg *cfg, void *dev_ws, size_t dev
     return TRI_OK;
 }
 
+namespace {
+// The static workspace as each device addresses it, and whether a pool lives in it.
+constexpr int MAX_STATIC_DEVICES = 64;
+struct StaticWs { void *ptr = nullptr; bool in_use = false; };
+StaticWs g_static[MAX_STATIC_DEVICES];
+std::mutex g_static_mu;
+}  // namespace
+
+extern "C" int tri_pool_create_static(const tri_pool_cfg *cfg, void *pinned_ws, size_t pinned_ws_bytes, tri_pool **out)
+{
+    uint32_t mrb, cr, ldc;
+    uint64_t sc;
+    size_t up;
+    int rc = derive(cfg, &mrb, &cr, &ldc, &sc, &up);
+    if (rc) return rc;
+    if (!pinned_ws || !out) return tri_fail(TRI_EINVAL, "pinned_ws / out is NULL (this call allocates no pinned memory either)");
+    const size_t need = carve(*cfg, mrb, cr, ldc, sc, up, nullptr, nullptr);
+    if (need > TRI_STATIC_WS_BYTES)
+        return tri_fail(TRI_ENOMEM, "this configuration needs %zu bytes of device workspace, the static workspace holds %u: "
+                                    "make it smaller (score_capacity, items_per_step, max_outstanding) or use tri_pool_create",
+                        need, (unsigned)TRI_STATIC_WS_BYTES);
+    int dev = 0;
+    HIP_TRY(hipGetDevice(&dev));
+    if (dev < 0 || dev >= MAX_STATIC_DEVICES) return tri_fail(TRI_EINVAL, "device %d: the static workspace is kept for devices 0..%d", dev, MAX_STATIC_DEVICES - 1);
+    std::lock_guard<std::mutex> lk(g_static_mu);
+    StaticWs &W = g_static[dev];
+    if (!W.ptr) {                               // once per device, with that device current
+        void *p = nullptr;
+        HIP_TRY(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+        if (!p) return tri_fail(TRI_EHIP, "hipGetSymbolAddress returned no address for the static workspace");
+        W.ptr = p;
+    }
+    if (W.in_use) return tri_fail(TRI_EAGAIN, "the static workspace of device %d holds a living pool: destroy that one first", dev);
+    // Whatever an earlier pool left is cleared, up to the candidate buffer (whose entries are always written
+    // before they are read, under counts the step itself produces).  A fill kernel, not a memset.
+    TriDevWs lay{};
+    carve(*cfg, mrb, cr, ldc, sc, up, (uint8_t *)W.ptr, &lay);
+    const size_t head = (size_t)((uint8_t *)lay.scores - (uint8_t *)W.ptr);
+    hipStream_t s = (hipStream_t)cfg->hip_stream;
+    HIP_TRY(tri_launch_fill_u32(s, (uint32_t *)W.ptr, 0u, head / 4));
+    HIP_TRY(hipStreamSynchronize(s));
+    rc = tri_pool_create(cfg, W.ptr, TRI_STATIC_WS_BYTES, pinned_ws, pinned_ws_bytes, out);
+    if (rc) return rc;
+    (*out)->static_dev = dev;
+    W.in_use = true;
+    return TRI_OK;
+}
+
 extern "C" int tri_pool_destroy(tri_pool *P)
 {
     if (!P) return tri_fail(TRI_EINVAL, "pool is NULL");
     for (tri_index *ix : P->indexes)
         if (ix) return tri_fail(TRI_EINVAL, "destroy the pool's indexes first");
     drop_graphs(P);
+    if (P->static_dev >= 0) {
+        std::lock_guard<std::mutex> lk(g_static_mu);
+        g_static[P->static_dev].in_use = false;
+    }
     for (uint32_t i = 0; i < RING; ++i) {
         if (P->ring[i].done) (void)hipEventDestroy(P->ring[i].done);
         for (uint32_t j = 0; j < N_EV; ++j)
