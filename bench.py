@@ -28,13 +28,8 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0   # MI355X published HBM3E bandwidth
-# HBM bytes one launch of the list-scan kernel moves at configuration 4, measured with rocprofv3 --pmc
-# FETCH_SIZE / WRITE_SIZE (each scaled by the same counter's reading for a 1 GiB device copy); the runs
-# are summarised in profiles/scan_kernel_config4.txt.  Not measurable from inside this script.
-MEASURED_TRAFFIC_BYTES = {4: 14.373e9}
-# The same for one launch of the graph engine's step kernel in the default graph workload
-# (profiles/graph_step_kernel.txt).
-GRAPH_TRAFFIC_BYTES = 0.914e9
+# (The HBM traffic per launch -- rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE -- cannot be measured from inside this
+# script: it is read from the summaries under profiles/, see traffic_from_profile.)
 
 
 def log(msg):
@@ -54,12 +49,325 @@ def one_omp_thread():
         omp.omp_set_num_threads(before)
 
 
+def traffic_from_profile(name, sources):
+    """The measured HBM traffic per launch that a rocprofv3 summary under profiles/ records, valid only while the
+    kernel sources it was measured on are unchanged: the summary carries the SHA-256 of those sources, and a
+    mismatch (a kernel was edited after the counters were collected) makes the figure null instead of stale.
+    Returns (bytes or None, provenance dict)."""
+    import hashlib
+    path = os.path.join(ROOT, "profiles", name)
+    prov = {"file": f"profiles/{name}"}
+    if not os.path.exists(path):
+        prov["status"] = "no such summary"
+        return None, prov
+    fields = {}
+    for line in open(path):
+        if line.startswith("@"):                      # machine-readable lines: "@key = value"
+            key, _, val = line[1:].partition("=")
+            fields[key.strip()] = val.strip()
+    h = hashlib.sha256()
+    for src in sources:
+        h.update(open(os.path.join(ROOT, "paper_2512_02281_amd", "csrc", src), "rb").read())
+    prov["profiled_commit"] = fields.get("profiled_commit")
+    prov["profiled_on"] = fields.get("profiled_on")
+    if fields.get("sources_sha256") != h.hexdigest():
+        prov["status"] = "stale: the kernel sources changed after these counters were collected"
+        return None, prov
+    prov["status"] = "current: the kernel sources are the profiled ones"
+    return float(fields["traffic_bytes_per_launch"]), prov
+
+
+def batch_config(number, args, tri, workloads, torch, headline):
+    """One batch configuration (0, 1, 2 or 4): build its index, time the step loop, recall, CPU oracle.
+    headline: the full measurement (configuration 4 by default); otherwise a shorter one whose result is nested
+    under "configs" of the headline's line."""
+    cfg = workloads.CONFIGS[number]
+    if args.queries_per_step and headline:
+        import dataclasses
+        cfg = dataclasses.replace(cfg, n_queries=args.queries_per_step)
+    t_start = time.time()
+    log(f"workload {cfg.name}: generating {cfg.n_base} x {cfg.dim}")
+    if number in (0, 1):
+        base_np, queries_np, rows = workloads.make_config01(cfg)
+        base_t = torch.from_numpy(base_np).cuda()
+        queries_t = torch.from_numpy(queries_np).cuda()
+        dtype, metric, tdtype = tri.TRI_F32, tri.TRI_L2, "f32"
+        k = np.full(cfg.n_queries, cfg.k, dtype=np.uint32)
+        nprobe = np.full(cfg.n_queries, cfg.nprobe, dtype=np.uint32)
+    else:
+        base_t, queries_t, rows = workloads.make_config_f16(cfg, device="cuda")
+        dtype, metric, tdtype = tri.TRI_F16, tri.TRI_IP, "f16"
+        if number == 2:
+            k, nprobe = workloads.hetero_params(cfg.n_queries, cfg.seed_params)
+        else:
+            k = np.full(cfg.n_queries, cfg.k, dtype=np.uint32)
+            nprobe = np.full(cfg.n_queries, cfg.nprobe, dtype=np.uint32)
+    torch.cuda.synchronize()
+    Q = cfg.n_queries
+    kmax = int(k.max())
+    items = int(nprobe.sum())
+    steps = args.steps if headline else max(20, args.steps)
+    warmup = args.warmup if headline else 5
+
+    pool = tri.Pool(slots=Q, items_per_step=items, lists_per_query_step=0, kmax=max(kmax, 16),
+                    nprobe_max=int(nprobe.max()), max_indexes=1, max_total_lists=cfg.nlist, max_nlist=cfg.nlist,
+                    max_dim=cfg.dim, max_outstanding=Q * 8, coarse_rows=Q, flags=tri.TRI_FLAG_PROFILE_SCAN,
+                    score_capacity=(1 << 31) if number == 4 else (1 << 30), own_stream=True)
+    log("building the index (untimed)")
+    t_b = time.time()
+    init = base_t[torch.from_numpy(rows).cuda()].float().cpu().numpy()
+    index = pool.build_index(base_t, cfg.dim, cfg.nlist, dtype, metric, cfg.train_iters, centroids=init)
+    info = tri.ivf_info(index)
+    log(f"index built in {time.time() - t_b:.1f}s; longest list {info['max_list_len']}")
+    metric_arr = np.full(Q, metric, dtype=np.uint32)
+    es = 2 if dtype == tri.TRI_F16 else 4
+    qptr, pitch = queries_t.data_ptr(), cfg.dim * es
+    queries_host = np.ascontiguousarray(queries_t.cpu().numpy())
+    host_q = tri.make_queries(index, queries_host, k, nprobe, metric_arr)
+
+    def one_batch(from_host):
+        if from_host:
+            tickets, rc = tri.search_submit_batch(pool.handle, host_q)
+        else:
+            tickets, rc = tri.search_submit_batch_dev(pool.handle, index, qptr, pitch, Q, k, nprobe, metric_arr)
+        assert rc == tri.TRI_OK and tickets.shape[0] == Q
+        launches = 0
+        while True:
+            st = tri.search_step(pool.handle)
+            launches += st.items > 0
+            if st.running == st.retired and st.pending_low == 0 and st.pending_high == 0:
+                break                         # every running query retires in the step just enqueued
+            assert launches < 10000
+        return tickets, launches
+
+    def drain(tickets):
+        ids, dist, n_out, status = tri.search_poll_batch(pool.handle, tickets, kmax)
+        assert np.all(status == tri.TRI_OK), "a query of a finished batch was not pollable"
+        return ids, dist, n_out
+
+    if args.copy_calibration_mib and headline:
+        src = torch.ones(args.copy_calibration_mib << 18, dtype=torch.float32, device="cuda")
+        dst = torch.empty_like(src)
+        dst.copy_(src)                      # reads and writes copy_calibration_mib MiB each
+        torch.cuda.synchronize()
+        del src, dst
+    # context beside the vendor's peak: what a plain streaming read of the same base vectors achieves here
+    stream_gbs = tri.tri_stream_read_bandwidth(base_t, 3) if base_t.numel() * base_t.element_size() >= (1 << 20) else None
+    if stream_gbs:
+        log(f"plain streaming read of the base ({base_t.numel() * base_t.element_size() / 1e9:.2f} GB): {stream_gbs:.0f} GB/s")
+    # Settling, untimed and independent of --warmup: the first few hundred milliseconds under load run about
+    # 7 % slower than the steady state (clocks ramping up), whatever is executed.
+    log("settling 0.6 s under load")
+    t_settle = time.perf_counter()
+    while time.perf_counter() - t_settle < 0.6:
+        tickets, launches_per_batch = one_batch(args.host_queries)
+        tri.search_sync(pool.handle)
+        drain(tickets)
+    log(f"warmup {warmup}")
+    last = None
+    for _ in range(max(warmup, 1)):
+        tickets, launches_per_batch = one_batch(args.host_queries)
+        tri.search_sync(pool.handle)
+        last = drain(tickets)
+    tri.tri_pool_kernel_times(pool.handle, reset=True)
+
+    def timed(n_steps, from_host):
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        inflight = []
+        for i in range(n_steps):
+            tickets, _ = one_batch(from_host)
+            inflight.append(tickets)
+            if len(inflight) > 2:                 # results of two batches ago are pollable by now or very soon
+                t_old = inflight.pop(0)
+                ids, dist, n_out, status = tri.search_poll_batch(pool.handle, t_old, kmax)
+                pending = t_old[status == tri.TRI_EAGAIN]
+                if pending.size:
+                    inflight.insert(0, pending)
+        tri.search_sync(pool.handle)
+        for t_old in inflight:
+            drain(t_old)
+        torch.cuda.synchronize()
+        return time.perf_counter() - t0
+
+    def repetitions(n_reps, from_host):
+        """One batch at a time, first submit to last result on the host, a synchronisation between repetitions:
+        the per-batch end-to-end time (median and minimum over the repetitions)."""
+        out = []
+        for _ in range(n_reps):
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            tickets, _ = one_batch(from_host)
+            tri.search_sync(pool.handle)
+            drain(tickets)
+            out.append((time.perf_counter() - t0) * 1e3)
+        out = np.asarray(out)
+        return {"repetitions": n_reps, "median_ms": round(float(np.median(out)), 4), "min_ms": round(float(out.min()), 4),
+                "queries_per_s_at_median": round(Q / float(np.median(out)) * 1e3, 1)}
+
+    # The timed region: exactly `steps` steps between synchronisations, batches pipelined (results of a batch are
+    # polled while later ones run).  The three launches of the list scan of every step are bracketed by HIP events
+    # on the pool's stream (their durations for the roofline figure); the other stages are not.
+    log(f"timing {steps} steps")
+    total_s = timed(steps, args.host_queries)
+    ms_per_step = total_s * 1e3 / steps
+    qps = Q * steps / total_s
+    kt = tri.tri_pool_kernel_times(pool.handle)
+    # the same loop with the query vectors submitted from host memory: the PCIe-inclusive rate (never `value`)
+    timed(3, not args.host_queries)
+    other_s = timed(steps, not args.host_queries)
+    host_s, dev_s = (total_s, other_s) if args.host_queries else (other_s, total_s)
+    # one batch at a time: median and minimum of the end-to-end time of a batch
+    reps_dev = repetitions(max(20, steps // 2), False)
+    reps_host = repetitions(max(20, steps // 2), True)
+    # stage breakdown: a short run afterwards with every stage bracketed
+    tri.tri_pool_set_profiling(pool.handle, tri.TRI_FLAG_PROFILE)
+    tri.tri_pool_kernel_times(pool.handle, reset=True)
+    timed(10, args.host_queries)
+    ks = tri.tri_pool_kernel_times(pool.handle)
+    step_launch = None
+    if headline:
+        # the same loop with the step replayed from its recording (Sec. 3.2), then kernel by kernel, both unprofiled
+        tri.tri_pool_set_profiling(pool.handle, 0)
+        tri.tri_pool_set_replay(pool.handle, True)
+        timed(5, args.host_queries)
+        n_cmp = max(10, steps // 4)
+        replay_ms = timed(n_cmp, args.host_queries) * 1e3 / n_cmp
+        tri.tri_pool_set_replay(pool.handle, False)
+        timed(5, args.host_queries)
+        eager_ms = timed(n_cmp, args.host_queries) * 1e3 / n_cmp
+        log(f"step replayed from its recording: {replay_ms:.3f} ms/step; kernel by kernel, no events: {eager_ms:.3f} ms/step")
+        step_launch = {"replayed_graph_ms_per_step": round(replay_ms, 4), "kernel_by_kernel_ms_per_step": round(eager_ms, 4),
+                       "note": "same loop, unprofiled"}
+    tri.tri_pool_set_profiling(pool.handle, tri.TRI_FLAG_PROFILE_SCAN)
+    nl = max(kt.scan_launches, 1)
+    sample_ms, thr_ms, main_ms = kt.sample_ms / nl, kt.threshold_ms / nl, kt.scan_ms / nl
+    main_b, list_b, tile_b = kt.scan_unique_bytes / nl, kt.scan_list_bytes / nl, kt.scan_vector_bytes / nl
+    row_bytes = -(-cfg.dim * es // 128) * 128
+    stage_ms = sample_ms + thr_ms + main_ms
+    achieved = list_b / (stage_ms * 1e-3) / 1e9 if stage_ms > 0 else 0.0
+    main_achieved = main_b / (main_ms * 1e-3) / 1e9 if main_ms > 0 else 0.0
+    sample_b = list_b - main_b
+    log(f"{ms_per_step:.3f} ms/step, {qps:.0f} q/s; scan stage {stage_ms:.3f} ms (sample {sample_ms:.3f} + thresholds {thr_ms:.3f} + main "
+        f"{main_ms:.3f}) for {list_b / 1e9:.2f} GB -> {achieved:.0f} GB/s; main launch alone {main_achieved:.0f} GB/s; stages ms/step (extra run): "
+        f"admit {ks.admit_ms / ks.steps:.3f} coarse {ks.coarse_ms / ks.steps:.3f} pack {ks.pack_ms / ks.steps:.3f} sample {ks.sample_ms / ks.steps:.3f} "
+        f"thresholds {ks.threshold_ms / ks.steps:.3f} scan {ks.scan_ms / ks.steps:.3f} select {ks.select_ms / ks.steps:.3f}")
+
+    # ---- recall of the returned lists against exact search (torch matmul on the GPU, harness only)
+    recall = None
+    if args.recall_sample:
+        ids, dist, n_out = last
+        rs = np.random.default_rng(77).choice(Q, size=min(args.recall_sample, Q), replace=False)
+        qs = queries_t[torch.from_numpy(rs).cuda()]
+        hits = tot = 0
+        for j, qi in enumerate(rs):
+            kk = int(k[qi])
+            if metric == tri.TRI_IP:
+                sc = (base_t @ qs[j]).float()
+                top = torch.topk(sc, kk).indices
+            else:
+                sc = ((base_t - qs[j]) ** 2).sum(dim=1)
+                top = torch.topk(sc, kk, largest=False).indices
+            hits += len(set(top.cpu().numpy().tolist()) & set(ids[qi, :kk].tolist()))
+            tot += kk
+        recall = hits / tot
+        log(f"recall@k on {rs.size} queries: {recall:.4f}")
+
+    # ---- the CPU oracle on a bounded sample of the same batch, same box
+    cpu = None
+    n_cpu = args.cpu_sample if args.cpu_sample >= 0 else {4: 1024, 2: 1024, 1: 1024, 0: 100}[number]
+    if not headline:
+        n_cpu = min(n_cpu, 512)
+    if n_cpu:
+        import oracle
+        log("exporting the index and copying the base to the host for the CPU oracle")
+        cent, off, lids = tri.ivf_export(index)
+        base_host = base_t.cpu().numpy()
+        oidx = oracle.Index(base_host, cent, off, lids)
+        sel = np.arange(0, Q, max(1, Q // n_cpu))[:n_cpu]
+        qh = queries_host[sel]
+        tc0 = time.perf_counter()
+        out = oracle.search_batch(oidx, qh, k[sel], nprobe[sel], metric_arr[sel])
+        tc = time.perf_counter() - tc0
+        cpu = {"value": round(sel.size / tc, 3), "unit": "queries/s", "cores": out["threads"], "kind": "oracle",
+               "sample": f"{sel.size} queries of the same batch (every {max(1, Q // n_cpu)}-th), {tc:.1f} s of wall time"}
+        if headline:
+            # the same oracle held to one thread, on a smaller sample sized from the rate just measured
+            n_one = int(min(sel.size, max(8, 6.0 * sel.size / tc / max(1, out["threads"]))))
+            one = sel[:: max(1, sel.size // n_one)][:n_one]
+            with one_omp_thread():
+                t1 = time.perf_counter()
+                out1 = oracle.search_batch(oidx, queries_host[one], k[one], nprobe[one], metric_arr[one])
+                t1 = time.perf_counter() - t1
+            if out1["threads"] == 1:
+                cpu["one_core"] = {"value": round(one.size / t1, 3), "unit": "queries/s",
+                                   "sample": f"{one.size} of those queries, {t1:.1f} s"}
+        log(f"cpu oracle: {cpu}")
+        del base_host, oidx
+
+    traffic, traffic_prov = (None, None)
+    if number == 4 and not args.queries_per_step:
+        traffic, traffic_prov = traffic_from_profile("scan_kernel_config4.txt", ["scan.hip", "select.hip", "tri_common.h", "tri_mfma.h"])
+    cache_note = None
+    if list_b < 4e9:
+        cache_note = ("the probed lists of a step are %.2f GB, small enough to stay in the 256 MB last-level cache in part and re-read "
+                      "per 32-query tile: cache-assisted, not an HBM figure" % (list_b / 1e9))
+    result = {
+        "metric": "queries/sec at recall@k>=0.9 (1 GPU) + list-scan HBM GB/s as % of peak",
+        "value": round(qps, 1), "unit": "queries/s", "n_gpus": 1, "steps": steps, "warmup": warmup,
+        "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": tdtype, "data": "synthetic", "settle_s": 0.6,
+        "config": {"workload": f"configs[{number}] {cfg.name}: {cfg.n_base} x {cfg.dim} {tdtype}, nlist {cfg.nlist}, "
+                               f"{Q} queries/step, nprobe {int(nprobe.max()) if number != 2 else 'U{8..128}'}, "
+                               f"k {kmax if number != 2 else 'U{1,10,100}'}",
+                   "queries_per_step": Q, "items_per_step": items, "launches_per_step": launches_per_batch,
+                   "recall_at_k": None if recall is None else round(recall, 4),
+                   "recall_sample": min(args.recall_sample, Q),
+                   "longest_list": info["max_list_len"],
+                   "query_vectors": "host memory (PCIe-inclusive side measurement)" if args.host_queries else "device-resident"},
+        # PCIe-inclusive: query vectors copied from host memory at submit and fetched over the bus by the admitting
+        # step; results land in pinned host memory either way.  Never `value`.
+        "value_host_queries": {"value": round(Q * steps / host_s, 1), "unit": "queries/s", "ms_per_step": round(host_s * 1e3 / steps, 4),
+                               "device_resident_same_run": round(Q * steps / dev_s, 1)},
+        "per_batch_end_to_end": {"device_resident_queries": reps_dev, "host_queries": reps_host},
+        "roofline": {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": traffic, "traffic_source": traffic_prov,
+                     "kernel": "list-scan stage: scan_wave_kernel sample launch + slot_threshold_kernel + scan_wave_kernel main launch; "
+                               "every probed list once over the HIP-event time of the three",
+                     "avg_launch_ms": round(stage_ms, 4), "algorithmic_bytes_per_launch": int(list_b),
+                     "scan_stage": {"sample_ms": round(sample_ms, 4), "threshold_ms": round(thr_ms, 4), "main_ms": round(main_ms, 4),
+                                    "bytes_all_lists": int(list_b), "frac_whole": round(achieved / HBM_PEAK_GBS, 4)},
+                     "main_launch": {"kernel": "scan_wave_kernel (main launch)", "avg_launch_ms": round(main_ms, 4),
+                                     "algorithmic_bytes_per_launch": int(main_b), "achieved": round(main_achieved, 1),
+                                     "frac": round(main_achieved / HBM_PEAK_GBS, 4)},
+                     "sample_launch": {"avg_launch_ms": round(sample_ms, 4), "algorithmic_bytes_per_launch": int(sample_b),
+                                       "achieved": round(sample_b / (sample_ms * 1e-3) / 1e9, 1) if sample_ms > 0 else None},
+                     "streaming_read_GBs": None if stream_gbs is None else round(stream_gbs, 1),
+                     "tile_bytes_per_launch": int(tile_b),
+                     "items_per_launch": int(kt.scan_items / nl), "row_bytes": row_bytes, "note": cache_note},
+        "stages_ms_per_step": {"admit": round(ks.admit_ms / ks.steps, 4), "coarse": round(ks.coarse_ms / ks.steps, 4),
+                               "pack": round(ks.pack_ms / ks.steps, 4), "sample": round(ks.sample_ms / ks.steps, 4),
+                               "thresholds": round(ks.threshold_ms / ks.steps, 4),
+                               "scan": round(ks.scan_ms / ks.steps, 4), "select": round(ks.select_ms / ks.steps, 4),
+                               "note": "10 more steps, every stage bracketed"},
+        "step_launch": step_launch,
+        "cpu_baseline": cpu,
+        "wall_s_total": round(time.time() - t_start, 1),
+    }
+    pool.close()
+    del base_t, queries_t, pool
+    torch.cuda.empty_cache()
+    return result
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=100)
     ap.add_argument("--warmup", type=int, default=10)
-    ap.add_argument("--workload", default="config4", choices=["config4", "config2", "config1", "config3", "graph", "graph-stream"])
+    ap.add_argument("--workload", default="config4", choices=["config4", "config2", "config1", "config0", "config3", "graph", "graph-stream"])
+    ap.add_argument("--only-headline", action="store_true",
+                    help="config4: skip the shorter measurements of configurations 0-3 that the default run nests under \"configs\"")
     ap.add_argument("--graph-n", type=int, default=1_000_000, help="graph workload: database rows")
     ap.add_argument("--graph-slots", type=int, default=8192, help="graph workload: requests advanced per step")
     ap.add_argument("--graph-topm", type=int, default=128, help="graph workload: length of a request's candidate list")
@@ -71,9 +379,9 @@ def main():
                          "the path scales when more queries share each list read; never the headline value)")
     ap.add_argument("--stream-queries", type=int, default=100_000, help="config3: queries in the stream")
     ap.add_argument("--cpu-sample", type=int, default=-1, help="queries timed on the CPU oracle (0 = skip)")
-    ap.add_argument("--recall-sample", type=int, default=64, help="queries checked against exact search (graph workload: 4 x as many)")
+    ap.add_argument("--recall-sample", type=int, default=256, help="queries checked against exact search (graph workload: as many)")
     ap.add_argument("--host-queries", action="store_true",
-                    help="submit the query vectors from host memory (adds their PCIe transfer to every step; "
+                    help="submit the query vectors of the timed region from host memory (adds their PCIe transfer to every step; "
                          "a side measurement, never the headline value)")
     ap.add_argument("--copy-calibration-mib", type=int, default=0,
                     help="run one plain device copy of this many MiB before timing (a kernel of known traffic, "
@@ -101,230 +409,47 @@ def main():
         return graph_stream_bench(args, tri, torch)
     number = int(args.workload[-1])
     if number == 3:
-        return stream_bench(args, tri, workloads, torch)
-    cfg = workloads.CONFIGS[number]
-    if args.queries_per_step:
-        import dataclasses
-        cfg = dataclasses.replace(cfg, n_queries=args.queries_per_step)
-    t_start = time.time()
-    log(f"workload {cfg.name}: generating {cfg.n_base} x {cfg.dim}")
-    if number == 1:
-        base_np, queries_np, rows = workloads.make_config01(cfg)
-        base_t = torch.from_numpy(base_np).cuda()
-        queries_t = torch.from_numpy(queries_np).cuda()
-        dtype, metric, tdtype = tri.TRI_F32, tri.TRI_L2, "f32"
-        k = np.full(cfg.n_queries, cfg.k, dtype=np.uint32)
-        nprobe = np.full(cfg.n_queries, cfg.nprobe, dtype=np.uint32)
-    else:
-        base_t, queries_t, rows = workloads.make_config_f16(cfg, device="cuda")
-        dtype, metric, tdtype = tri.TRI_F16, tri.TRI_IP, "f16"
-        if number == 2:
-            k, nprobe = workloads.hetero_params(cfg.n_queries, cfg.seed_params)
-        else:
-            k = np.full(cfg.n_queries, cfg.k, dtype=np.uint32)
-            nprobe = np.full(cfg.n_queries, cfg.nprobe, dtype=np.uint32)
-    torch.cuda.synchronize()
-    Q = cfg.n_queries
-    kmax = int(k.max())
-    items = int(nprobe.sum())
-
-    pool = tri.Pool(slots=Q, items_per_step=items, lists_per_query_step=0, kmax=max(kmax, 16),
-                    nprobe_max=int(nprobe.max()), max_indexes=1, max_total_lists=cfg.nlist, max_nlist=cfg.nlist,
-                    max_dim=cfg.dim, max_outstanding=Q * 8, coarse_rows=Q, flags=tri.TRI_FLAG_PROFILE_SCAN,
-                    score_capacity=(1 << 31), own_stream=True)
-    log("building the index (untimed)")
-    t_b = time.time()
-    init = base_t[torch.from_numpy(rows).cuda()].float().cpu().numpy()
-    index = pool.build_index(base_t, cfg.dim, cfg.nlist, dtype, metric, cfg.train_iters, centroids=init)
-    info = tri.ivf_info(index)
-    log(f"index built in {time.time() - t_b:.1f}s; longest list {info['max_list_len']}")
-    metric_arr = np.full(Q, metric, dtype=np.uint32)
-    es = 2 if dtype == tri.TRI_F16 else 4
-    qptr, pitch = queries_t.data_ptr(), cfg.dim * es
-
-    host_q = None
-    if args.host_queries:
-        queries_host = np.ascontiguousarray(queries_t.cpu().numpy())
-        host_q = tri.make_queries(index, queries_host, k, nprobe, metric_arr)
-
-    def one_batch():
-        if host_q is not None:
-            tickets, rc = tri.search_submit_batch(pool.handle, host_q)
-        else:
-            tickets, rc = tri.search_submit_batch_dev(pool.handle, index, qptr, pitch, Q, k, nprobe, metric_arr)
-        assert rc == tri.TRI_OK and tickets.shape[0] == Q
-        launches = 0
-        while True:
-            st = tri.search_step(pool.handle)
-            launches += st.items > 0
-            if st.running == st.retired and st.pending_low == 0 and st.pending_high == 0:
-                break                         # every running query retires in the step just enqueued
-            assert launches < 10000
-        return tickets, launches
-
-    def drain(tickets):
-        ids, dist, n_out, status = tri.search_poll_batch(pool.handle, tickets, kmax)
-        assert np.all(status == tri.TRI_OK), "a query of a finished batch was not pollable"
-        return ids, dist, n_out
-
-    if args.copy_calibration_mib:
-        src = torch.ones(args.copy_calibration_mib << 18, dtype=torch.float32, device="cuda")
-        dst = torch.empty_like(src)
-        dst.copy_(src)                      # reads and writes copy_calibration_mib MiB each
-        torch.cuda.synchronize()
-        del src, dst
-    # context beside the vendor's peak: what a plain streaming read of the same base vectors achieves here
-    stream_gbs = tri.tri_stream_read_bandwidth(base_t, 3)
-    log(f"plain streaming read of the base ({base_t.numel() * base_t.element_size() / 1e9:.2f} GB): {stream_gbs:.0f} GB/s")
-    # Settling, untimed and independent of --warmup: the first few hundred milliseconds under load run about
-    # 7 % slower than the steady state (clocks ramping up), whatever is executed.
-    log("settling 0.6 s under load")
-    t_settle = time.perf_counter()
-    while time.perf_counter() - t_settle < 0.6:
-        tickets, launches_per_batch = one_batch()
-        tri.search_sync(pool.handle)
-        drain(tickets)
-    log(f"warmup {args.warmup}")
-    last = None
-    for _ in range(max(args.warmup, 1)):
-        tickets, launches_per_batch = one_batch()
-        tri.search_sync(pool.handle)
-        last = drain(tickets)
-    tri.tri_pool_kernel_times(pool.handle, reset=True)
-
-    def timed(steps):
-        torch.cuda.synchronize()
-        t0 = time.perf_counter()
-        inflight = []
-        for i in range(steps):
-            tickets, _ = one_batch()
-            inflight.append(tickets)
-            if len(inflight) > 2:                 # results of two batches ago are pollable by now or very soon
-                t_old = inflight.pop(0)
-                ids, dist, n_out, status = tri.search_poll_batch(pool.handle, t_old, kmax)
-                pending = t_old[status == tri.TRI_EAGAIN]
-                if pending.size:
-                    inflight.insert(0, pending)
-        tri.search_sync(pool.handle)
-        for t_old in inflight:
-            drain(t_old)
-        torch.cuda.synchronize()
-        return time.perf_counter() - t0
-
-    # The timed region: the list scan of every step is bracketed by two HIP events (its duration for the
-    # roofline figure); the other stages are not.
-    log(f"timing {args.steps} steps")
-    total_s = timed(args.steps)
-    ms_per_step = total_s * 1e3 / args.steps
-    qps = Q * args.steps / total_s
-    kt = tri.tri_pool_kernel_times(pool.handle)
-    # stage breakdown: a short run afterwards with every stage bracketed
-    tri.tri_pool_set_profiling(pool.handle, tri.TRI_FLAG_PROFILE)
-    tri.tri_pool_kernel_times(pool.handle, reset=True)
-    timed(10)
-    ks = tri.tri_pool_kernel_times(pool.handle)
-    # the same loop with the step replayed from its recording (Sec. 3.2), then kernel by kernel, both unprofiled
-    tri.tri_pool_set_profiling(pool.handle, 0)
-    tri.tri_pool_set_replay(pool.handle, True)
-    timed(5)
-    replay_ms = timed(max(10, args.steps // 4)) * 1e3 / max(10, args.steps // 4)
-    tri.tri_pool_set_replay(pool.handle, False)
-    timed(5)
-    eager_ms = timed(max(10, args.steps // 4)) * 1e3 / max(10, args.steps // 4)
-    tri.tri_pool_set_profiling(pool.handle, tri.TRI_FLAG_PROFILE_SCAN)
-    log(f"step replayed from its recording: {replay_ms:.3f} ms/step; kernel by kernel, no events: {eager_ms:.3f} ms/step")
-    scan_ms = kt.scan_ms / max(kt.scan_launches, 1)
-    unique_b = kt.scan_unique_bytes / max(kt.scan_launches, 1)
-    tile_b = kt.scan_vector_bytes / max(kt.scan_launches, 1)
-    row_bytes = -(-cfg.dim * es // 128) * 128
-    achieved = unique_b / (scan_ms * 1e-3) / 1e9 if scan_ms > 0 else 0.0
-    log(f"{ms_per_step:.3f} ms/step, {qps:.0f} q/s; scan {scan_ms:.3f} ms/launch, unique {unique_b / 1e9:.2f} GB "
-        f"-> {achieved:.0f} GB/s; stages ms/step (extra run): admit {ks.admit_ms / ks.steps:.3f} coarse {ks.coarse_ms / ks.steps:.3f} "
-        f"pack {ks.pack_ms / ks.steps:.3f} sample {ks.sample_ms / ks.steps:.3f} scan {ks.scan_ms / ks.steps:.3f} select {ks.select_ms / ks.steps:.3f}")
-
-    # ---- recall of the returned lists against exact search (torch matmul on the GPU, harness only)
-    recall = None
-    if args.recall_sample:
-        ids, dist, n_out = last
-        rs = np.random.default_rng(77).choice(Q, size=min(args.recall_sample, Q), replace=False)
-        qs = queries_t[torch.from_numpy(rs).cuda()]
-        hits = tot = 0
-        for j, qi in enumerate(rs):
-            kk = int(k[qi])
-            if metric == tri.TRI_IP:
-                sc = (base_t @ qs[j]).float()
-                top = torch.topk(sc, kk).indices
-            else:
-                sc = ((base_t - qs[j]) ** 2).sum(dim=1)
-                top = torch.topk(sc, kk, largest=False).indices
-            hits += len(set(top.cpu().numpy().tolist()) & set(ids[qi, :kk].tolist()))
-            tot += kk
-        recall = hits / tot
-        log(f"recall@k on {rs.size} queries: {recall:.4f}")
-
-    # ---- the CPU oracle on a bounded sample of the same batch, same box
-    cpu = None
-    n_cpu = args.cpu_sample if args.cpu_sample >= 0 else {4: 1024, 2: 1024, 1: 1024}[number]
-    if n_cpu:
-        import oracle
-        log("exporting the index and copying the base to the host for the CPU oracle")
-        cent, off, lids = tri.ivf_export(index)
-        base_host = base_t.cpu().numpy()
-        oidx = oracle.Index(base_host, cent, off, lids)
-        sel = np.arange(0, Q, max(1, Q // n_cpu))[:n_cpu]
-        qh = queries_t.cpu().numpy()[sel]
-        tc0 = time.perf_counter()
-        out = oracle.search_batch(oidx, qh, k[sel], nprobe[sel], metric_arr[sel])
-        tc = time.perf_counter() - tc0
-        cpu = {"value": round(sel.size / tc, 3), "unit": "queries/s", "cores": out["threads"], "kind": "oracle",
-               "sample": f"{sel.size} queries of the same batch (every {max(1, Q // n_cpu)}-th), {tc:.1f} s of wall time"}
-        # the same oracle held to one thread, on a smaller sample sized from the rate just measured
-        n_one = int(min(sel.size, max(8, 6.0 * sel.size / tc / max(1, out["threads"]))))
-        one = sel[:: max(1, sel.size // n_one)][:n_one]
-        with one_omp_thread():
-            t1 = time.perf_counter()
-            out1 = oracle.search_batch(oidx, queries_t.cpu().numpy()[one], k[one], nprobe[one], metric_arr[one])
-            t1 = time.perf_counter() - t1
-        if out1["threads"] == 1:
-            cpu["one_core"] = {"value": round(one.size / t1, 3), "unit": "queries/s",
-                               "sample": f"{one.size} of those queries, {t1:.1f} s"}
-        log(f"cpu oracle: {cpu}")
-
-    result = {
-        "metric": "queries/sec at recall@k>=0.9 (1 GPU) + list-scan HBM GB/s as % of peak",
-        "value": round(qps, 1), "unit": "queries/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
-        "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": tdtype, "data": "synthetic", "settle_s": 0.6,
-        "config": {"workload": f"configs[{number}] {cfg.name}: {cfg.n_base} x {cfg.dim} {tdtype}, nlist {cfg.nlist}, "
-                               f"{Q} queries/step, nprobe {int(nprobe.max()) if number != 2 else 'U{8..128}'}, "
-                               f"k {kmax if number != 2 else 'U{1,10,100}'}",
-                   "queries_per_step": Q, "items_per_step": items, "launches_per_step": launches_per_batch,
-                   "recall_at_k": None if recall is None else round(recall, 4),
-                   "longest_list": info["max_list_len"],
-                   "query_vectors": "host memory (PCIe-inclusive side measurement)" if args.host_queries else "device-resident"},
-        "roofline": {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": MEASURED_TRAFFIC_BYTES.get(number),
-                     "streaming_read_GBs": round(stream_gbs, 1),
-                     "kernel": "scan_wave_kernel (main launch)", "avg_launch_ms": round(scan_ms, 4),
-                     "algorithmic_bytes_per_launch": int(unique_b), "tile_bytes_per_launch": int(tile_b),
-                     "items_per_launch": int(kt.scan_items / max(kt.scan_launches, 1)), "row_bytes": row_bytes},
-        "stages_ms_per_step": {"admit": round(ks.admit_ms / ks.steps, 4), "coarse": round(ks.coarse_ms / ks.steps, 4),
-                               "pack": round(ks.pack_ms / ks.steps, 4), "sample": round(ks.sample_ms / ks.steps, 4),
-                               "scan": round(ks.scan_ms / ks.steps, 4), "select": round(ks.select_ms / ks.steps, 4),
-                               "note": "10 more steps with every stage bracketed by events"},
-        "step_launch": {"replayed_graph_ms_per_step": round(replay_ms, 4), "kernel_by_kernel_ms_per_step": round(eager_ms, 4),
-                        "note": "same loop, unprofiled, after the timed region (which launches kernel by kernel with two events around the scan)"},
-        "cpu_baseline": cpu,
-        "wall_s_total": round(time.time() - t_start, 1),
-    }
-    pool.close()
+        print(json.dumps(stream_bench(args, tri, workloads, torch, brief=False)), flush=True)
+        return
+    result = batch_config(number, args, tri, workloads, torch, headline=True)
+    if number == 4 and not args.only_headline and not args.queries_per_step and not args.host_queries:
+        # the other configurations, shorter, in the same run: absolute queries/s, recall and the CPU oracle beside
+        # each; one compact record per configuration in the line, the full record of each on stderr
+        others = {}
+        for other in (0, 1, 2):
+            r = batch_config(other, args, tri, workloads, torch, headline=False)
+            log("full record of configs[%d]: %s" % (other, json.dumps(r)))
+            e2e = r["per_batch_end_to_end"]
+            others[str(other)] = {
+                "qps": r["value"], "ms_per_step": r["ms_per_step"], "launches_per_step": r["config"]["launches_per_step"],
+                "recall_at_k": r["config"]["recall_at_k"], "qps_host_queries": r["value_host_queries"]["value"],
+                "batch_ms_median_min": [e2e["device_resident_queries"]["median_ms"], e2e["device_resident_queries"]["min_ms"]],
+                "batch_ms_median_min_host_queries": [e2e["host_queries"]["median_ms"], e2e["host_queries"]["min_ms"]],
+                "scan_stage_GBs": r["roofline"]["achieved"], "scan_lists_GB": round(r["roofline"]["algorithmic_bytes_per_launch"] / 1e9, 3),
+                "cache_assisted": r["roofline"]["note"] is not None,
+                "cpu_oracle_qps": r["cpu_baseline"]["value"] if r["cpu_baseline"] else None,
+                "cpu_cores": r["cpu_baseline"]["cores"] if r["cpu_baseline"] else None,
+                "cpu_sample": int(r["cpu_baseline"]["sample"].split()[0]) if r["cpu_baseline"] else None}
+        r = stream_bench(args, tri, workloads, torch, brief=True)
+        log("full record of configs[3]: %s" % json.dumps(r))
+        runs = r["stream"]
+        others["3"] = {"saturation_qps": r["value"], "queries": args.stream_queries, "slots": 4096, "lists_per_query_step": 8,
+                       "query_vectors": "host memory",
+                       "open_loop": [{"offered_qps": x["offered_qps"], "qps": x["throughput_qps"],
+                                      "p50_p99_ms": x["latency_ms_p50_p99"]["all"],
+                                      "p50_p99_ms_cache_high_class": x["latency_ms_p50_p99"]["cache_high_class"]} for x in runs[1:4]],
+                       "cpu_oracle_qps": r["cpu_baseline"]["value"] if r["cpu_baseline"] else None,
+                       "cpu_cores": r["cpu_baseline"]["cores"] if r["cpu_baseline"] else None}
+        result["configs"] = others
     print(json.dumps(result), flush=True)
 
 
-def stream_bench(args, tri, workloads, torch):
+def stream_bench(args, tri, workloads, torch, brief):
     """Configuration 3: 70 % RAG queries (k ~ U{10..100}, nprobe 32, low class) over the 1M x 768 index,
     30 % prompt-cache lookups (k 1, nprobe 8, high class) over the 200k x 768 index, 4096 slots, 8 lists
-    per query and step."""
+    per query and step.  brief: saturation and the three open-loop rates only (the summary the default run
+    nests under "configs"); otherwise also the static-batch scheme, the step-boundary policies and the
+    replayed step.  Returns the result."""
     t_start = time.time()
     rag_cfg, cache_cfg = workloads.CONFIGS[2], workloads.CACHE_INDEX
     n, slots, p = args.stream_queries, 4096, 8
@@ -375,6 +500,12 @@ def stream_bench(args, tri, workloads, torch):
     for frac in (0.5, 0.8):
         runs.append(run(workloads.poisson_arrivals(n, frac * t_sat, 4003), f"Poisson arrivals at {frac} x saturation")[0])
     runs.append(run(workloads.poisson_arrivals(n, 1.0e5, 4003), "Poisson arrivals at 100,000 / s")[0])
+    if not brief:
+        more_stream_runs(runs, run, tri, pool, workloads, n, q, is_rag, t_sat)
+    return finish_stream(args, tri, pool, w, ir, ic, queries, is_rag, n, slots, p, runs, t_sat, kt, st, t_start)
+
+
+def more_stream_runs(runs, run, tri, pool, workloads, n, q, is_rag, t_sat):
     # the scheme continuous batching replaces (Sec. 3.2): a batch must drain before the next is admitted
     runs.append(run(np.zeros(n), "closed loop, static batches", static_batches=True)[0])
     for frac in (0.5, 0.8):
@@ -407,6 +538,9 @@ def stream_bench(args, tri, workloads, torch):
     tri.tri_pool_set_replay(pool.handle, False)
     tri.tri_pool_set_profiling(pool.handle, tri.TRI_FLAG_PROFILE)
 
+
+def finish_stream(args, tri, pool, w, ir, ic, queries, is_rag, n, slots, p, runs, t_sat, kt, st, t_start):
+    import torch
     cpu = None
     n_cpu = args.cpu_sample if args.cpu_sample >= 0 else 512
     if n_cpu:
@@ -446,7 +580,8 @@ def stream_bench(args, tri, workloads, torch):
         "wall_s_total": round(time.time() - t_start, 1),
     }
     pool.close()
-    print(json.dumps(result), flush=True)
+    torch.cuda.empty_cache()
+    return result
 
 
 def graph_bench(args, tri, torch):
@@ -517,7 +652,7 @@ def graph_bench(args, tri, torch):
         f"mean distance evaluations {ev.mean():.0f} per query")
     recall = None
     if args.recall_sample:
-        rs = np.random.default_rng(77).choice(Q, size=min(4 * args.recall_sample, Q), replace=False)
+        rs = np.random.default_rng(77).choice(Q, size=min(args.recall_sample, Q), replace=False)
         hits = 0
         for qi in rs:
             top = torch.topk((X @ Qv[int(qi)]).float(), k).indices.cpu().numpy().tolist()
@@ -542,6 +677,9 @@ def graph_bench(args, tri, torch):
                "sample": f"{sel.size} queries of the same batch (every {max(1, Q // n_cpu)}-th), {tc:.1f} s of wall time; "
                          f"{same} of them returned exactly the GPU's ids"}
         log(f"cpu oracle: {cpu}")
+    graph_traffic, graph_traffic_prov = (None, None)
+    if n == 1_000_000 and S == 8192:
+        graph_traffic, graph_traffic_prov = traffic_from_profile("graph_step_kernel.txt", ["graph_engine.hip"])
     result = {
         "metric": "queries/sec at recall@k>=0.9 (1 GPU) + list-scan HBM GB/s as % of peak",
         "value": round(qps, 1), "unit": "queries/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
@@ -555,7 +693,7 @@ def graph_bench(args, tri, torch):
                    "mean_extends_per_query": round(float(it.mean()), 2), "mean_evaluations_per_query": round(float(ev.mean()), 1),
                    "recall_at_k": None if recall is None else round(recall, 4), "query_vectors": "device-resident"},
         "roofline": {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": GRAPH_TRAFFIC_BYTES if n == 1_000_000 and S == 8192 else None, "kernel": "gx_step_kernel",
+                     "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": graph_traffic, "traffic_source": graph_traffic_prov, "kernel": "gx_step_kernel",
                      "avg_launch_ms": round(dist_ms, 5), "measured": "all slots stepped as one group (launches do not overlap)",
                      "avg_launch_ms_in_timed_region": round(kt_groups.step_kernel_ms / max(kt_groups.steps, 1), 5),
                      "algorithmic_bytes_per_launch": int(bytes_per_launch),

@@ -54,8 +54,9 @@ enum { TRI_F32 = 0, TRI_F16 = 1 };        /* storage type of an index's vectors 
 enum { TRI_CLASS_HIGH = 0, TRI_CLASS_LOW = 1 }; /* Sec. 3.3: prefill-side (latency critical) / decode-side requests */
 enum { TRI_FLAG_PROFILE = 1u,             /* bracket every stage of a step with HIP events (tri_pool_kernel_times)    */
        TRI_FLAG_KEEP_PROBES = 2u,         /* copy each query's probe list back so search_probes() can return it      */
-       TRI_FLAG_PROFILE_SCAN = 4u,        /* bracket only the list scan (two events): scan_ms and the scan_* counters
-                                             of tri_pool_kernel_times are filled, the other stage times stay zero    */
+       TRI_FLAG_PROFILE_SCAN = 4u,        /* bracket only the three launches of the list scan (four events): sample_ms,
+                                             threshold_ms, scan_ms and the scan_* counters of tri_pool_kernel_times
+                                             are filled, the other stage times stay zero                              */
        TRI_FLAG_GRAPH = 8u };             /* Sec. 3.2 (fixed-shape step captured once, replayed): the launch sequence
                                              of a step is recorded as a HIP graph at three captured sizes (1/16, 1/4 and
                                              all of slots and items_per_step; once per size, step in flight and set of
@@ -386,8 +387,9 @@ typedef struct {
     double admit_ms;         /* query rows into slots                                              */
     double coarse_ms;        /* centroid contraction + top-nprobe selection                        */
     double pack_ms;          /* work-item array and tile table                                     */
-    double sample_ms;        /* sample scan + per-query thresholds                                  */
-    double scan_ms;          /* list scan                                                          */
+    double sample_ms;        /* sample launch of the list scan (the first 64 vectors of every probed list) */
+    double threshold_ms;     /* per-query thresholds from the sample (and its candidates)           */
+    double scan_ms;          /* main launch of the list scan                                       */
     double select_ms;        /* per-query top-k merge, result copy-out enqueue                     */
     uint64_t scan_launches;  /* list-scan kernel launches                                          */
     uint64_t scan_vector_bytes; /* bytes of inverted-list vectors those launches had to read: each
@@ -395,6 +397,8 @@ typedef struct {
                                    are scored by the sample launch and not counted here             */
     uint64_t scan_unique_bytes; /* same, each distinct list counted once per step                  */
     uint64_t scan_items;     /* work items scanned                                                 */
+    uint64_t scan_list_bytes;   /* bytes of every distinct probed list, whole, once per step: what the three
+                                   launches of the scan stage together have to read                 */
 } tri_kernel_times;
 int tri_pool_kernel_times(tri_pool *pool, tri_kernel_times *out /*[host] out*/, int reset);
 /* Switch the profiling of the steps enqueued from now on: flags = 0, TRI_FLAG_PROFILE or

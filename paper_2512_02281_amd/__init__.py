@@ -68,9 +68,10 @@ class tri_step_stats(ctypes.Structure):
 
 class tri_kernel_times(ctypes.Structure):
     _fields_ = [("steps", ctypes.c_uint64), ("admit_ms", ctypes.c_double), ("coarse_ms", ctypes.c_double),
-                ("pack_ms", ctypes.c_double), ("sample_ms", ctypes.c_double), ("scan_ms", ctypes.c_double), ("select_ms", ctypes.c_double),
+                ("pack_ms", ctypes.c_double), ("sample_ms", ctypes.c_double), ("threshold_ms", ctypes.c_double),
+                ("scan_ms", ctypes.c_double), ("select_ms", ctypes.c_double),
                 ("scan_launches", ctypes.c_uint64), ("scan_vector_bytes", ctypes.c_uint64),
-                ("scan_unique_bytes", ctypes.c_uint64), ("scan_items", ctypes.c_uint64)]
+                ("scan_unique_bytes", ctypes.c_uint64), ("scan_items", ctypes.c_uint64), ("scan_list_bytes", ctypes.c_uint64)]
 
 
 class tri_policy(ctypes.Structure):

@@ -290,3 +290,18 @@ hipError_t tri_build_cluster_means(hipStream_t s, int dtype, const void *rows, u
                            list_off, perm, normalise, cent_f32);
     return hipGetLastError();
 }
+
+// ------------------------------------------------------------------------------ inverse of the id array
+// inv[ids[p]] = p: where base row `id` is stored (ids is a permutation of 0..n-1).
+__global__ void invert_perm_kernel(const uint32_t *__restrict__ ids, uint64_t n, uint32_t *__restrict__ inv)
+{
+    const uint64_t p = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (p < n) inv[ids[p]] = (uint32_t)p;
+}
+
+hipError_t tri_build_invert_perm(hipStream_t s, const uint32_t *ids, uint64_t n, uint32_t *inv)
+{
+    if (n == 0) return hipSuccess;
+    hipLaunchKernelGGL(invert_perm_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, ids, n, inv);
+    return hipGetLastError();
+}

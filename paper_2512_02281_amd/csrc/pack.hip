@@ -157,7 +157,7 @@ __global__ void pack_emit_kernel(const uint8_t *__restrict__ upload,
 //     each over a contiguous span of the order, in two launches: FINAL = false leaves every span's
 //     totals in block_tot, FINAL = true adds the totals of the spans before its own and writes.
 #define PACK_SCAN_BLOCKS 16
-#define PACK_SCAN_SUMS 8      // values per span in block_tot (7 used)
+#define PACK_SCAN_SUMS 9      // values per span in block_tot (8 used)
 
 template <bool FINAL>
 __global__ __launch_bounds__(1024) void pack_scan_kernel(const uint32_t *__restrict__ hist, uint32_t n_order,
@@ -173,7 +173,7 @@ __global__ __launch_bounds__(1024) void pack_scan_kernel(const uint32_t *__restr
                                                          TriStepDev *__restrict__ step_host)
 {
     __shared__ uint32_t s_items[1024], s_tiles[1024], s_lists[1024], s_stiles[1024];
-    __shared__ uint64_t s_scores[1024], s_tbytes[1024], s_ubytes[1024];
+    __shared__ uint64_t s_scores[1024], s_tbytes[1024], s_ubytes[1024], s_lbytes[1024];
     const uint32_t t = threadIdx.x;
     const uint32_t min_chunk = hdr->min_chunk;
     const uint32_t span = (n_order + gridDim.x - 1) / gridDim.x;
@@ -181,7 +181,7 @@ __global__ __launch_bounds__(1024) void pack_scan_kernel(const uint32_t *__restr
     const uint32_t per = (span + 1023) / 1024;
     const uint32_t i0 = min(s0 + t * per, s1), i1 = min(i0 + per, s1);
     uint32_t items = 0, tiles = 0, lists = 0, stiles = 0;
-    uint64_t sc = 0, tb = 0, ub = 0;
+    uint64_t sc = 0, tb = 0, ub = 0, lb = 0;
     // (entries {list, length, row bytes, chunks} are static; only the item counts are gathered, several at once)
     for (uint32_t ib = i0; ib < i1; ib += 8) {
         uint4 o[8];
@@ -205,30 +205,31 @@ __global__ __launch_bounds__(1024) void pack_scan_kernel(const uint32_t *__restr
                 sc += (uint64_t)c * 2u * ((len + TRI_VB - 1) / TRI_VB * TRI_VB);
                 tb += bytes * nt;
                 ub += bytes;
+                lb += (uint64_t)len * o[u].z;
             }
         }
     }
     s_items[t] = items; s_tiles[t] = tiles; s_lists[t] = lists; s_stiles[t] = stiles;
-    s_scores[t] = sc; s_tbytes[t] = tb; s_ubytes[t] = ub;
+    s_scores[t] = sc; s_tbytes[t] = tb; s_ubytes[t] = ub; s_lbytes[t] = lb;
     __syncthreads();
     // Hillis-Steele inclusive scan over the 1024 thread totals
     for (uint32_t d = 1; d < 1024; d <<= 1) {
         uint32_t a = 0, b = 0, l = 0, e = 0;
-        uint64_t x = 0, y = 0, z = 0;
+        uint64_t x = 0, y = 0, z = 0, w8 = 0;
         if (t >= d) {
             a = s_items[t - d]; b = s_tiles[t - d]; l = s_lists[t - d]; e = s_stiles[t - d];
-            x = s_scores[t - d]; y = s_tbytes[t - d]; z = s_ubytes[t - d];
+            x = s_scores[t - d]; y = s_tbytes[t - d]; z = s_ubytes[t - d]; w8 = s_lbytes[t - d];
         }
         __syncthreads();
         s_items[t] += a; s_tiles[t] += b; s_lists[t] += l; s_stiles[t] += e;
-        s_scores[t] += x; s_tbytes[t] += y; s_ubytes[t] += z;
+        s_scores[t] += x; s_tbytes[t] += y; s_ubytes[t] += z; s_lbytes[t] += w8;
         __syncthreads();
     }
     if (!FINAL) {
         if (t == 1023) {
             uint64_t *o = block_tot + blockIdx.x * PACK_SCAN_SUMS;
             o[0] = s_items[t]; o[1] = s_tiles[t]; o[2] = s_lists[t]; o[3] = s_stiles[t];
-            o[4] = s_scores[t]; o[5] = s_tbytes[t]; o[6] = s_ubytes[t];
+            o[4] = s_scores[t]; o[5] = s_tbytes[t]; o[6] = s_ubytes[t]; o[7] = s_lbytes[t];
         }
         return;
     }
@@ -269,6 +270,7 @@ __global__ __launch_bounds__(1024) void pack_scan_kernel(const uint32_t *__restr
         step_dev->total_scores = base[4] + s_scores[t];
         step_dev->tile_vec_bytes = base[5] + s_tbytes[t];
         step_dev->unique_vec_bytes = base[6] + s_ubytes[t];
+        step_dev->list_bytes = base[7] + s_lbytes[t];
         if (step_host) *step_host = *step_dev;       // a copy for the host's statistics (pinned host memory)
         for (uint32_t k = 0; k < 2 * TRI_SCAN_CLASSES; ++k) tile_counter[k] = 0;
     }

@@ -771,6 +771,29 @@ hipError_t tri_launch_threshold(const TriLaunchCtx &c, const TriDevWs &ws, uint3
     return hipGetLastError();
 }
 
+// Squared L2 distance of a stored row to a query row in the difference form, sum of (x_i - q_i)^2, by the 32
+// lanes of a half-wavefront: lane l takes the 16-byte pieces l, l + 32, ... of both rows, the partial sums are
+// combined by a butterfly (a fixed order, the same in every lane).  fp32 arithmetic; fp16 inputs widen exactly.
+template <typename T>
+__device__ __forceinline__ float sel_l2_diff_form(const uint8_t *__restrict__ x, const uint8_t *__restrict__ q, uint32_t row_bytes,
+                                                  uint32_t l32)
+{
+    constexpr int PER = 16 / sizeof(T);
+    float acc = 0.f;
+    for (uint32_t o = l32 * 16; o < row_bytes; o += 32 * 16) {
+        const uint4 xv = *(const uint4 *)(x + o), qv = *(const uint4 *)(q + o);
+        const T *xe = (const T *)&xv, *qe = (const T *)&qv;
+#pragma unroll
+        for (int i = 0; i < PER; ++i) {
+            const float d = (float)xe[i] - (float)qe[i];
+            acc = __builtin_fmaf(d, d, acc);
+        }
+    }
+#pragma unroll
+    for (int d = 16; d > 0; d >>= 1) acc += __shfl_xor(acc, d, 32);
+    return acc;
+}
+
 // ------------------------------------------------------------------------------------------------
 // Slot merge: one workgroup per running slot of the step.  Candidates = the (score, position) pairs
 // the scan kept for the slot's work items of this step, one segment per (item, chunk), + its running
@@ -783,7 +806,7 @@ __global__ __launch_bounds__(TRI_SEL_THREADS) void slot_merge_kernel(
     const uint32_t *__restrict__ glist_voff, const float *__restrict__ cand, float *__restrict__ topk_score,
     uint32_t *__restrict__ topk_id, uint32_t *__restrict__ topk_count, uint32_t kmax,
     uint32_t *__restrict__ res_block, const uint32_t *__restrict__ probe, uint32_t nprobe_max,
-    uint32_t *__restrict__ res_probes)
+    uint32_t *__restrict__ res_probes, const uint8_t *__restrict__ slot_query, uint32_t slot_row_bytes)
 {
     __shared__ SelShared sh;
     const TriStepHdr *hdr = (const TriStepHdr *)upload;
@@ -811,6 +834,30 @@ __global__ __launch_bounds__(TRI_SEL_THREADS) void slot_merge_kernel(
     uint32_t n;
     const uint64_t *best = sel_block_topk(sh, src, seg_of, meta.k, desc, &n);
     // (all reads of the running buffer are done: sel_block_topk ends with a barrier)
+    if (e.retire_idx >= 0 && !desc && n > 0) {
+        // The scan scores squared L2 in the expanded form |x|^2 + |q|^2 - 2 x.q, whose fp32 error grows with
+        // the norms, not with the distance: fine for choosing the k best, too coarse for the distance that is
+        // handed back when a query nearly coincides with a stored vector.  The k survivors of a retiring
+        // query are scored again in the difference form (k rows re-read: nothing beside the scan) and put in
+        // the order of those scores (equal scores by ascending id, as everywhere).
+        const TriIndexDev &ix = indexes[meta.index];
+        const uint8_t *qrow = slot_query + (size_t)e.slot * slot_row_bytes;
+        uint64_t *fresh = best == sh.pool ? sh.small : sh.pool;             // (n <= kmax <= SEL_SMALL)
+        const uint32_t l32 = threadIdx.x & 31;
+        for (uint32_t i = threadIdx.x >> 5; i < n; i += TRI_SEL_THREADS / 32) {
+            const uint32_t id = (uint32_t)(best[i] & 0xFFFFFFFFu);
+            const uint8_t *x = (const uint8_t *)ix.vecs + (size_t)ix.inv[id] * ix.row_bytes;
+            const float d2 = ix.dtype == 1u ? sel_l2_diff_form<_Float16>(x, qrow, ix.row_bytes, l32)
+                                            : sel_l2_diff_form<float>(x, qrow, ix.row_bytes, l32);
+            if (l32 == 0) fresh[i] = ((uint64_t)sel_key(d2, 0u) << 32) | id;
+        }
+        __syncthreads();
+        if (fresh != sh.pool) {
+            for (uint32_t i = threadIdx.x; i < n; i += TRI_SEL_THREADS) sh.pool[i] = fresh[i];
+            __syncthreads();
+        }
+        best = sel_pool_topk(sh, n, n);
+    }
     if (e.retire_idx >= 0) {
         uint32_t *rec = res_block + (size_t)e.retire_idx * (1u + 2u * kmax);
         if (threadIdx.x == 0) rec[0] = n;
@@ -840,6 +887,7 @@ hipError_t tri_launch_merge(const TriLaunchCtx &c, const TriDevWs &ws, uint32_t 
     hipLaunchKernelGGL(slot_merge_kernel, dim3(grid_plan), dim3(TRI_SEL_THREADS), 0, c.stream, ws.upload, ws.slot_meta,
                        ws.indexes, ws.item_glist, ws.item_score_off, ws.item_sorted_pos, ws.surv_count,
                        ws.glist_len, ws.glist_voff, ws.scores, ws.topk_score, ws.topk_id, ws.topk_count, c.kmax,
-                       ws.res_block, ws.probe, c.nprobe_max, keep_probes ? ws.res_probes : (uint32_t *)nullptr);
+                       ws.res_block, ws.probe, c.nprobe_max, keep_probes ? ws.res_probes : (uint32_t *)nullptr,
+                       ws.slot_query, c.slot_row_bytes);
     return hipGetLastError();
 }

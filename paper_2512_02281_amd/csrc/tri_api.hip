@@ -48,7 +48,7 @@ namespace {
     } while (0)
 
 constexpr uint32_t RING = 4;          // steps that may be in flight before search_step waits
-constexpr uint32_t N_EV = 7;          // profile events per step
+constexpr uint32_t N_EV = 8;          // profile events per step
 constexpr uint32_t N_SHAPES = 3;      // captured sizes of a step: 1/16, 1/4 and all of the pool's slots and items
 
 inline int64_t now_ns()
@@ -225,7 +225,7 @@ size_t carve(const tri_pool_cfg &c, uint32_t max_row_bytes, uint32_t coarse_rows
     CARVE(glist_voff, uint32_t *, G * 4)
     CARVE(glist_index, uint32_t *, G * 4)
     CARVE(glist_order, uint4 *, G * 16)
-    CARVE(pack_tot, uint64_t *, 16 * 8 * 8)
+    CARVE(pack_tot, uint64_t *, 16 * 9 * 8)
     CARVE(upload, uint8_t *, upload_bytes)
     CARVE(coarse_scores, float *, (size_t)coarse_rows * coarse_ldc * 4)
     CARVE(item_glist, uint32_t *, W * 4)
@@ -348,23 +348,27 @@ int reap(tri_pool *P, bool block, uint32_t *finished)
             ++fin;
         }
         if (R->profiled || R->profiled_scan) {
+            // events: 0 block pulled, 1 admitted, 2 ranked, 3 packed, 4 sample scanned, 5 thresholds set, 6 lists
+            // scanned, 7 merged; with only the scan profiled, 3..6 exist
             float ms[N_EV - 1] = {};
             if (R->profiled)
                 for (uint32_t i = 0; i + 1 < N_EV; ++i) HIP_TRY(hipEventElapsedTime(&ms[i], R->ev[i], R->ev[i + 1]));
             else if (R->had_scan)
-                HIP_TRY(hipEventElapsedTime(&ms[4], R->ev[4], R->ev[5]));
+                for (uint32_t i = 3; i < 6; ++i) HIP_TRY(hipEventElapsedTime(&ms[i], R->ev[i], R->ev[i + 1]));
             const TriStepDev *sd = (const TriStepDev *)(R->down_host + P->down_step_off);
             P->times.steps += 1;
             P->times.admit_ms += ms[0];
             P->times.coarse_ms += ms[1];
             P->times.pack_ms += ms[2];
             P->times.sample_ms += ms[3];
-            P->times.scan_ms += ms[4];
-            P->times.select_ms += ms[5];
+            P->times.threshold_ms += ms[4];
+            P->times.scan_ms += ms[5];
+            P->times.select_ms += ms[6];
             if (R->had_scan) {
                 P->times.scan_launches += 1;
                 P->times.scan_vector_bytes += sd->tile_vec_bytes;
                 P->times.scan_unique_bytes += sd->unique_vec_bytes;
+                P->times.scan_list_bytes += sd->list_bytes;
                 P->times.scan_items += R->n_items;
             }
         }
@@ -670,6 +674,7 @@ extern "C" int ivf_build_bytes(const ivf_params *p, uint64_t n, size_t *dev_byte
     o += round_up_sz((size_t)n * rb, 256);                 // vectors
     o += round_up_sz(((size_t)n + TRI_VB) * 4, 256);       // |x|^2 (+ one block of slack for tail reads)
     o += round_up_sz((size_t)n * 4, 256);                  // ids
+    o += round_up_sz((size_t)n * 4, 256);                  // stored position of every base row
     o += round_up_sz(((size_t)p->nlist + 1) * 4, 256);     // list offsets
     o += round_up_sz((size_t)p->nlist * rb, 256);          // centroids
     o += round_up_sz((size_t)p->nlist * 4, 256);           // |c|^2
@@ -809,6 +814,7 @@ extern "C" int ivf_build(tri_pool *P, const ivf_params *p, const void *base, uin
     uint8_t *vecs = m;              m += round_up_sz((size_t)n * rb, 256);
     float *vnorm = (float *)m;      m += round_up_sz(((size_t)n + TRI_VB) * 4, 256);
     uint32_t *ids = (uint32_t *)m;  m += round_up_sz((size_t)n * 4, 256);
+    uint32_t *inv = (uint32_t *)m;  m += round_up_sz((size_t)n * 4, 256);
     uint32_t *loff = (uint32_t *)m; m += round_up_sz(((size_t)nlist + 1) * 4, 256);
     uint8_t *cent = m;              m += round_up_sz((size_t)nlist * rb, 256);
     float *cnorm = (float *)m;
@@ -900,6 +906,7 @@ extern "C" int ivf_build(tri_pool *P, const ivf_params *p, const void *base, uin
                     ldc, chunk, assign);
     if (rc) return rc;
     HIP_TRY(tri_build_partition(s, assign, n, nlist, block_hist, nblocks, list_len, loff, ids));
+    HIP_TRY(tri_build_invert_perm(s, ids, n, inv));
     for (uint64_t r0 = 0; r0 < n; r0 += (1u << 20)) {
         const uint64_t cnt = std::min<uint64_t>(1u << 20, n - r0);
         HIP_TRY(tri_build_pad_rows(s, dtype, dbase, dim, dim, ids + r0, 0, 0, 1, cnt, vecs + r0 * rb, dpad));
@@ -923,7 +930,7 @@ extern "C" int ivf_build(tri_pool *P, const ivf_params *p, const void *base, uin
     if (!ix) return tri_fail(TRI_ENOMEM, "out of host memory");
     ix->pool = P; ix->id = id; ix->p = *p; ix->n = n; ix->dpad = dpad; ix->row_bytes = rb;
     ix->list_base = P->total_lists; ix->max_list_len = maxlen; ix->ids_dev = ids; ix->list_off_dev = loff;
-    ix->dev = TriIndexDev{vecs, vnorm, ids, loff, cent, cnorm, dim, dpad, nlist, p->dtype, rb, ix->list_base, maxlen, 0, n};
+    ix->dev = TriIndexDev{vecs, vnorm, ids, loff, cent, cnorm, inv, dim, dpad, nlist, p->dtype, rb, ix->list_base, maxlen, 0, n};
     hipError_t e = hipMemcpy(P->ws.indexes + id, &ix->dev, sizeof(TriIndexDev), hipMemcpyHostToDevice);
     if (e == hipSuccess) e = hipMemcpy(P->ws.glist_len + ix->list_base, h_len.data(), (size_t)nlist * 4, hipMemcpyHostToDevice);
     if (e == hipSuccess) e = hipMemcpy(P->ws.glist_voff + ix->list_base, h_off.data(), (size_t)nlist * 4, hipMemcpyHostToDevice);
@@ -1433,15 +1440,16 @@ int step_locked(tri_pool *P, tri_step_stats *st)
         }
         if (prof) HIP_TRY(hipEventRecord(R.ev[2], s));
         HIP_TRY(tri_launch_pack(P->ctx, W, n_items, P->total_lists, P->n_order));
-        if (prof) HIP_TRY(hipEventRecord(R.ev[3], s));
+        if (prof || (prof_scan && n_items)) HIP_TRY(hipEventRecord(R.ev[3], s));
         // thresholds: score a sample of every probed list, k-th best of each slot's sample
         if (n_items) HIP_TRY(tri_launch_scan(P->ctx, P->ws, P->attached_row_bytes, P->scan_class_mask, true));
-        if (n_items) HIP_TRY(tri_launch_threshold(P->ctx, P->ws, n_plan));
         if (prof || (prof_scan && n_items)) HIP_TRY(hipEventRecord(R.ev[4], s));
-        if (n_items) HIP_TRY(tri_launch_scan(P->ctx, P->ws, P->attached_row_bytes, P->scan_class_mask, false));
+        if (n_items) HIP_TRY(tri_launch_threshold(P->ctx, P->ws, n_plan));
         if (prof || (prof_scan && n_items)) HIP_TRY(hipEventRecord(R.ev[5], s));
+        if (n_items) HIP_TRY(tri_launch_scan(P->ctx, P->ws, P->attached_row_bytes, P->scan_class_mask, false));
+        if (prof || (prof_scan && n_items)) HIP_TRY(hipEventRecord(R.ev[6], s));
         HIP_TRY(tri_launch_merge(P->ctx, W, n_plan, keep_probes));
-        if (prof) HIP_TRY(hipEventRecord(R.ev[6], s));
+        if (prof) HIP_TRY(hipEventRecord(R.ev[7], s));
     }
     HIP_TRY(hipEventRecord(R.done, s));
     R.in_use = true;

@@ -19,6 +19,7 @@ struct TriIndexDev {
     const uint32_t *list_off;// [nlist+1] first stored position of each list
     const void *centroids;   // [nlist] rows of pitch row_bytes, index dtype
     const float *cnorm;      // |c|^2 per centroid, fp32
+    const uint32_t *inv;     // stored position of every base row: inv[ids[p]] = p
     uint32_t dim, dpad, nlist, dtype;
     uint32_t row_bytes;      // dpad * element size, multiple of 128
     uint32_t list_base;      // number of this index's list 0 in the pool-wide list numbering
@@ -122,7 +123,8 @@ struct TriStepDev {
     uint32_t pad_;
     uint64_t total_scores;
     uint64_t tile_vec_bytes;    // sum over tiles of list_len * row_bytes
-    uint64_t unique_vec_bytes;  // sum over touched lists of list_len * row_bytes
+    uint64_t unique_vec_bytes;  // sum over touched lists of (list_len - sample) * row_bytes: what the main launch must read
+    uint64_t list_bytes;        // sum over touched lists of list_len * row_bytes: what the whole scan stage must read
 };
 
 // Device workspace of a pool, carved once at creation.
@@ -142,7 +144,7 @@ struct TriDevWs {
     uint32_t *glist_voff;     // [max_total_lists] first stored position inside its index
     uint32_t *glist_index;    // [max_total_lists]
     TriStepDev *step_host;    // NULL, or where the step totals are mirrored for the host (pinned host memory)
-    uint64_t *pack_tot;       // [16][8] per-span totals of the pack prefix sums
+    uint64_t *pack_tot;       // [16][9] per-span totals of the pack prefix sums
     uint4 *glist_order;       // [max_total_lists] attached lists by descending byte length (scan order):
                               //   {pool-wide list number, length, row bytes, 0}
     // per-step upload block (device copy)
@@ -253,6 +255,7 @@ hipError_t tri_build_partition(hipStream_t s, const uint32_t *assign, uint64_t n
                                uint32_t *block_hist /*[nblocks][nlist]*/, uint32_t nblocks,
                                uint32_t *list_len_tmp /*[nlist]*/, uint32_t *list_off /*[nlist+1]*/,
                                uint32_t *perm /*[nrows]*/);
+hipError_t tri_build_invert_perm(hipStream_t s, const uint32_t *ids, uint64_t n, uint32_t *inv);
 hipError_t tri_build_cluster_means(hipStream_t s, int dtype, const void *rows, uint32_t dpad,
                                    const uint32_t *list_off, const uint32_t *perm, uint32_t nlist, int normalise,
                                    float *cent_f32 /*[nlist][dpad] in/out*/);

@@ -3,11 +3,15 @@
 Top-k id sets must equal the oracle's except among ties, where scores agree within the
 tolerance; returned scores must agree with the oracle's score of the same id.
 
-Tolerance model (relative ``tol`` = 1e-4 for fp32 indexes, 2e-3 for fp16 indexes, plus an
-absolute term for scores near zero): |g - o| <= tol * |o| + ABS_EPS * scale, where
-scale = |q|^2 + |x|^2 for L2 (cancellation of the expanded form |x|^2 + |q|^2 - 2 q.x in
-fp32 leaves an error proportional to the norms, not to the distance) and |q| |x| for the
-inner product (fp32 accumulation of d products).  ABS_EPS = 4e-6 = 64 * 2^-24.
+Tolerance model (relative ``tol`` = 1e-4 for fp32 indexes, 2e-3 for fp16 indexes):
+* returned scores: |g - o| <= tol * |o| for squared L2 -- the library hands back distances computed in the
+  difference form, whose fp32 error is relative to the distance itself, so a distance of exactly zero must
+  come back as zero --, and tol * |o| + ABS_EPS * |q| |x| for the inner product (fp32 accumulation of d
+  products of either sign: the error is relative to sum |q_i x_i|, not to the possibly cancelling sum);
+* which candidates make the list: the scan ranks squared L2 in the expanded form |x|^2 + |q|^2 - 2 q.x, whose
+  fp32 error is proportional to the norms, not to the distance, so the tie band around the k-th score keeps
+  an absolute term ABS_EPS * (|q|^2 + |x|^2) beside tol * |tau| (inner product: ABS_EPS * |q| |x|).
+ABS_EPS = 4e-6 = 64 * 2^-24.
 
 ``strict`` mode: tolerance zero -- ids must equal the oracle's list exactly (same order,
 ties by id) and scores must be equal as fp32 values (used where the arithmetic is exact).
@@ -21,6 +25,13 @@ ABS_EPS = 4e-6
 
 def tolerance_for(dtype_code: int) -> float:
     return 1e-4 if dtype_code == 0 else 2e-3
+
+
+def score_allowance(metric, tol, oracle_scores, scale):
+    """How far a returned score may be from the oracle's: purely relative for squared L2, relative plus the
+    absolute term for the inner product (scale = |q| |x| per returned row)."""
+    rel = tol * np.abs(oracle_scores)
+    return rel if metric == METRIC_L2 else rel + ABS_EPS * scale
 
 
 def _norm2(v):
@@ -64,7 +75,7 @@ def check_result(q, base, metric, k, got_ids, got_dist, got_n, cand_ids, cand_sc
     qn2 = _norm2(q)
     xn2 = (base[ids].astype(np.float64) ** 2).sum(axis=1)
     scale = qn2 + xn2 if metric == METRIC_L2 else np.sqrt(qn2 * xn2)
-    allowed = tol * np.abs(o_of_id) + ABS_EPS * scale
+    allowed = score_allowance(metric, tol, o_of_id, scale)
     err = np.abs(dist - o_of_id)
     assert np.all(err <= allowed), \
         f"score off by {err.max():.3e} (allowed {allowed[np.argmax(err)]:.3e}) for id {ids[np.argmax(err)]}"

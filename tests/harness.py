@@ -112,7 +112,7 @@ def _settled_by_the_batch_oracle(oidx, base_np, vecs, k, nprobe, metric, ids, di
         xn2 = (base_np[want["ids"][j, :n]].astype(np.float64) ** 2).sum(axis=1)
         scale = qn2 + xn2 if m == 0 else np.sqrt(qn2 * xn2)
         pad = np.inf if m == 0 else -np.inf
-        if np.all(np.abs(got - o) <= tol * np.abs(o) + checker.ABS_EPS * scale) and \
+        if np.all(np.abs(got - o) <= checker.score_allowance(m, tol, o, scale)) and \
                 np.all(np.asarray(dist[i, n:kk], dtype=np.float64) == pad):
             settled.add(i)
     return settled

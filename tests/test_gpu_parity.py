@@ -157,6 +157,41 @@ def test_config2_fp16_inner_product_heterogeneous(scale):
         harness.compare_with_oracle(oidx, base, sub_vecs, 10, 16, 0, ids2, dist2, n2, probes2)
 
 
+@pytest.mark.parametrize("dtype", ["f32", "f16"])
+def test_l2_distances_of_duplicates_and_near_duplicates(dtype):
+    """Squared L2 comes back in the difference form: a query that IS a stored vector gets distance exactly zero,
+    one that nearly is gets its tiny distance to the relative tolerance (the expanded form the scan ranks with
+    would return noise of the size of the norms' rounding there), and no distance is negative."""
+    tri = harness.lib()
+    rng = np.random.default_rng(91)
+    np_dtype = np.float32 if dtype == "f32" else np.float16
+    n, d, nlist = 20_000, 96 if dtype == "f32" else 200, 32
+    centres = rng.normal(0.0, 2.0, size=(nlist, d))
+    base = (3.0 + centres[rng.integers(0, nlist, n)] + rng.normal(0.0, 1.0, size=(n, d))).astype(np_dtype)
+    rows = rng.choice(n, 90, replace=False)
+    exact = base[rows[:30]]
+    near = (base[rows[30:60]].astype(np.float64) + rng.normal(0.0, 2e-3 if dtype == "f32" else 1e-2, size=(30, d))).astype(np_dtype)
+    far = (base[rows[60:]].astype(np.float64) + rng.normal(0.0, 1.0, size=(30, d))).astype(np_dtype)
+    queries = np.ascontiguousarray(np.concatenate([exact, near, far]))
+    with harness.default_pool(tri, slots=64, lists_per_query_step=3, max_dim=d, max_nlist=nlist, max_total_lists=nlist) as pool:
+        idx = pool.build_index(base, d, nlist, tri.TRI_F32 if dtype == "f32" else tri.TRI_F16, tri.TRI_L2, 4,
+                               centroids=base[rng.choice(n, nlist, replace=False)].astype(np.float32))
+        oidx = harness.oracle_index(tri, idx, base)
+        q = tri.make_queries(idx, queries, 10, 8, tri.TRI_L2)
+        ids, dist, n_out, probes, _ = harness.run_all(tri, pool, q)
+        assert np.all(dist[:, :10] >= 0.0)
+        assert np.all(dist[:30, 0] == 0.0)
+        for i in range(30):                      # the stored vector itself heads the list (or an identical twin of it)
+            assert np.array_equal(base[ids[i, 0]], exact[i])
+        true_near = ((base[rows[30:60]].astype(np.float64) - near.astype(np.float64)) ** 2).sum(axis=1)
+        assert true_near.min() > 0.0
+        _say(f"L2 {dtype}: near-duplicate distances {true_near.min():.3e}..{true_near.max():.3e}, "
+             f"returned within {np.max(np.abs(dist[30:60, 0] - true_near) / true_near):.2e} relative")
+        assert np.all(ids[30:60, 0] == rows[30:60])
+        rep = harness.compare_with_oracle(oidx, base, queries, 10, 8, 0, ids, dist, n_out, probes)
+        assert rep["checked"] == 90
+
+
 def test_scheduling_does_not_change_results():
     """Continuous batching must leave results intact: one batch, one list per step, a short task
     array, fewer slots than queries (slot reuse), and mid-stream arrival all give bit-identical
