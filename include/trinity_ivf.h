@@ -84,7 +84,10 @@ typedef struct {
     uint32_t max_outstanding;      /* tickets alive at once (pending + running + finished, not yet polled)  */
     uint32_t coarse_rows;          /* new queries ranked against centroids per launch (0 = default 1024)    */
     uint32_t flags;                /* TRI_FLAG_*                                                           */
-    uint64_t score_capacity;       /* 4-byte words of the step's candidate buffer (2 per scanned vector and query); 0 = W*2048 */
+    uint64_t score_capacity;       /* 4-byte words of the step's candidate buffer: 2 per candidate the scan's filter lets
+                                      through; every query of a step gets a region of it sized by what is expected to pass
+                                      (about k * list length / 64 with a wide margin), see tri_pool_set_candidate_reserve.
+                                      0 = 2 * (1024 * slots + 32 * W) */
     void *hip_stream;              /* hipStream_t all work is enqueued on (NULL = the null stream)          */
 } tri_pool_cfg;
 
@@ -415,6 +418,14 @@ int tri_pool_set_replay(tri_pool *pool, int on);
  * peak.  dev_sink [device]: 4 writable bytes.  Synchronous. */
 int tri_stream_read_bandwidth(const void *dev_buf, size_t bytes, void *dev_sink, void *hip_stream, uint32_t repeats,
                               double *gb_per_s /*[host] out*/);
+
+/* Candidate pairs reserved per query and step: 0 (default) = the estimate from k and the index's list lengths;
+ * otherwise exactly `pairs` (never more than the query's lists hold).  A query whose scan lets more pass than was
+ * reserved still gets the exact result: the top-k merge notices and scores that query's lists of the step again
+ * itself, which is slow.  tri_pool_candidate_rescans counts how often that has happened since the pool was created
+ * (synchronises with the pool's stream). */
+int tri_pool_set_candidate_reserve(tri_pool *pool, uint32_t pairs);
+int tri_pool_candidate_rescans(tri_pool *pool, uint64_t *rescans /*[host] out*/);
 
 /* Testing aid: the next search_step that has work to enqueue fails as if one of its launches had
  * failed (TRI_EHIP), after it has admitted its queries.  A pool in which a step failed half-way is

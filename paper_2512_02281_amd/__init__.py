@@ -104,7 +104,7 @@ EXPORTS = ["tri_pool_workspace_bytes", "tri_pool_create", "tri_pool_create_stati
            "search_run_stream", "search_set_policy", "search_get_policy", "tri_policy_split", "tri_policy_slack_order",
            "tri_policy_feedback", "search_set_feedback", "search_report_signals", "search_get_feedback",
            "tri_pool_kernel_times", "tri_pool_set_profiling", "tri_pool_set_replay", "tri_stream_read_bandwidth",
-           "tri_pool_inject_failure", "tri_last_error", "tri_version"]
+           "tri_pool_inject_failure", "tri_pool_set_candidate_reserve", "tri_pool_candidate_rescans", "tri_last_error", "tri_version"]
 
 
 def _load():
@@ -121,6 +121,8 @@ def _load():
     lib.tri_pool_create.argtypes = [P(tri_pool_cfg), vp, sz, vp, sz, P(vp)]
     lib.tri_pool_create_static.argtypes = [P(tri_pool_cfg), vp, sz, P(vp)]
     lib.tri_pool_inject_failure.argtypes = [vp]
+    lib.tri_pool_set_candidate_reserve.argtypes = [vp, u32]
+    lib.tri_pool_candidate_rescans.argtypes = [vp, P(u64)]
     lib.tri_pool_destroy.argtypes = [vp]
     lib.ivf_build_bytes.argtypes = [P(ivf_params), u64, P(sz)]
     lib.ivf_build_tmp_bytes.argtypes = [P(ivf_params), u64, ctypes.c_int, P(sz)]
@@ -205,6 +207,16 @@ def tri_pool_create_static(cfg: tri_pool_cfg, pinned_ptr: int, pinned_bytes: int
     _check(_lib.tri_pool_create_static(ctypes.byref(cfg), ctypes.c_void_p(pinned_ptr), pinned_bytes, ctypes.byref(out)),
            "tri_pool_create_static")
     return out.value
+
+
+def tri_pool_set_candidate_reserve(pool: int, pairs: int) -> None:
+    _check(_lib.tri_pool_set_candidate_reserve(ctypes.c_void_p(pool), pairs), "tri_pool_set_candidate_reserve")
+
+
+def tri_pool_candidate_rescans(pool: int) -> int:
+    out = ctypes.c_uint64(0)
+    _check(_lib.tri_pool_candidate_rescans(ctypes.c_void_p(pool), ctypes.byref(out)), "tri_pool_candidate_rescans")
+    return int(out.value)
 
 
 def tri_pool_inject_failure(pool: int) -> None:

@@ -152,7 +152,7 @@ __global__ void pack_emit_kernel(const uint8_t *__restrict__ upload,
 
 // (2) scan.  Exclusive prefix sums, taken over the attached lists in the order of descending byte
 //     length (so the longest tiles are dealt out first and the step ends on the shortest), of: items
-//     per list (-> list_start), tiles per list (-> tile_base), padded scores per list (-> score_base).
+//     per list (-> list_start) and tiles per list (-> tile_base, stile_base).
 //     Also the step totals and the reset of the work-queue heads.  Up to PACK_SCAN_BLOCKS workgroups,
 //     each over a contiguous span of the order, in two launches: FINAL = false leaves every span's
 //     totals in block_tot, FINAL = true adds the totals of the spans before its own and writes.
@@ -165,7 +165,6 @@ __global__ __launch_bounds__(1024) void pack_scan_kernel(const uint32_t *__restr
                                                          uint32_t *__restrict__ list_start,
                                                          uint32_t *__restrict__ tile_base,
                                                          uint32_t *__restrict__ stile_base,
-                                                         uint64_t *__restrict__ score_base,
                                                          TriStepDev *__restrict__ step_dev,
                                                          uint32_t *__restrict__ tile_counter,
                                                          const TriStepHdr *__restrict__ hdr,
@@ -239,7 +238,6 @@ __global__ __launch_bounds__(1024) void pack_scan_kernel(const uint32_t *__restr
         for (int v = 0; v < PACK_SCAN_SUMS - 1; ++v) base[v] += block_tot[b * PACK_SCAN_SUMS + v];
     uint32_t it = (uint32_t)base[0] + s_items[t] - items, ti = (uint32_t)base[1] + s_tiles[t] - tiles,
              sti = (uint32_t)base[3] + s_stiles[t] - stiles;
-    uint64_t so = base[4] + s_scores[t] - sc;
     for (uint32_t ib = i0; ib < i1; ib += 8) {
         uint4 o[8];
         uint32_t cnt[8];
@@ -254,12 +252,10 @@ __global__ __launch_bounds__(1024) void pack_scan_kernel(const uint32_t *__restr
             list_start[g] = it;
             tile_base[g] = ti;
             stile_base[g] = sti;
-            score_base[g] = so;
             if (c) {
                 it += c;
                 ti += (c + TRI_QT - 1) / TRI_QT * ((len + tri_chunk_vecs(len, min_chunk) - 1) / tri_chunk_vecs(len, min_chunk));
                 sti += len ? (c + TRI_QT - 1) / TRI_QT : 0;
-                so += (uint64_t)c * 2u * ((len + TRI_VB - 1) / TRI_VB * TRI_VB);
             }
         }
     }
@@ -276,20 +272,17 @@ __global__ __launch_bounds__(1024) void pack_scan_kernel(const uint32_t *__restr
     }
 }
 
-// (3) scatter: one thread per item -> list-sorted slot array and the item's score segment.
+// (3) scatter: one thread per item -> list-sorted slot array.
 __global__ void pack_scatter_kernel(const TriStepHdr *__restrict__ hdr, const uint32_t *__restrict__ item_glist,
                                     const uint32_t *__restrict__ item_slot, const uint32_t *__restrict__ item_rank,
-                                    const uint32_t *__restrict__ list_start, const uint64_t *__restrict__ score_base,
-                                    const uint32_t *__restrict__ glist_len, uint32_t *__restrict__ sorted_slot,
-                                    uint64_t *__restrict__ item_score_off, uint32_t *__restrict__ item_sorted_pos)
+                                    const uint32_t *__restrict__ list_start, uint32_t *__restrict__ sorted_slot,
+                                    uint32_t *__restrict__ item_sorted_pos)
 {
     const uint32_t i = blockIdx.x * blockDim.x + threadIdx.x;
     if (i >= hdr->n_items) return;
     const uint32_t g = item_glist[i], r = item_rank[i];
-    const uint32_t npad = (glist_len[g] + TRI_VB - 1) / TRI_VB * TRI_VB;
     sorted_slot[list_start[g] + r] = item_slot[i];
     item_sorted_pos[i] = list_start[g] + r;
-    item_score_off[i] = score_base[g] + (uint64_t)r * 2u * npad;
 }
 
 // (4) tiles: one thread per list of the pool-wide table.  A list longer than its chunk length is cut into
@@ -297,7 +290,7 @@ __global__ void pack_scatter_kernel(const TriStepHdr *__restrict__ hdr, const ui
 //     list also gets its sample tiles (first TRI_SAMPLE_VECS vectors, one per group of queries).
 __global__ void pack_tiles_kernel(uint32_t total_lists, const uint32_t *__restrict__ hist,
                                   const uint32_t *__restrict__ list_start, const uint32_t *__restrict__ tile_base,
-                                  const uint32_t *__restrict__ stile_base, const uint64_t *__restrict__ score_base,
+                                  const uint32_t *__restrict__ stile_base,
                                   const uint32_t *__restrict__ glist_len, const uint32_t *__restrict__ glist_voff,
                                   const uint32_t *__restrict__ glist_index, const TriIndexDev *__restrict__ indexes,
                                   const TriStepHdr *__restrict__ hdr, TriTile *__restrict__ tiles,
@@ -310,7 +303,6 @@ __global__ void pack_tiles_kernel(uint32_t total_lists, const uint32_t *__restri
     const uint32_t len = glist_len[g];
     if (!c || !len) return;
     const TriIndexDev &ix = indexes[glist_index[g]];
-    const uint32_t npad = (len + TRI_VB - 1) / TRI_VB * TRI_VB;
     const uint32_t nt = (c + TRI_QT - 1) / TRI_QT;
     const uint32_t chunk_vecs = tri_chunk_vecs(len, min_chunk);
     const uint32_t nchunks = (len + chunk_vecs - 1) / chunk_vecs;
@@ -324,11 +316,11 @@ __global__ void pack_tiles_kernel(uint32_t total_lists, const uint32_t *__restri
         tl.vec_addr = (uint64_t)(uintptr_t)ix.vecs + (uint64_t)(voff + v0) * ix.row_bytes;
         tl.vnorm_addr = (uint64_t)(uintptr_t)(ix.vnorm + voff + v0);
         tl.vec_count = min(chunk_vecs, len - v0);
-        tl.pitch = 2u * npad;
+        tl.pitch = 0;
         tl.vec_begin = v0;
         tl.chunk = ch;
+        tl.out_off = (uint64_t)voff + v0;            // (candidates carry the stored position of their vector)
         for (uint32_t q = 0; q < nt; ++q) {
-            tl.out_off = score_base[g] + (uint64_t)q * TRI_QT * 2u * npad + 2u * v0;
             tl.item_pos = list_start[g] + q * TRI_QT;
             tl.nq = min((uint32_t)TRI_QT, c - q * TRI_QT);
             tiles[w++] = tl;
@@ -363,17 +355,16 @@ hipError_t tri_launch_pack(const TriLaunchCtx &c, const TriDevWs &ws, uint32_t g
     const uint32_t nb = std::min<uint32_t>(PACK_SCAN_BLOCKS, (n_order + 1023) / 1024);
     if (nb > 1)
         hipLaunchKernelGGL(pack_scan_kernel<false>, dim3(nb), dim3(1024), 0, c.stream, ws.hist, n_order, ws.glist_order,
-                           ws.list_start, ws.tile_base, ws.stile_base, ws.score_base, ws.step_dev, ws.tile_counter,
+                           ws.list_start, ws.tile_base, ws.stile_base, ws.step_dev, ws.tile_counter,
                            hdr, ws.pack_tot, (TriStepDev *)nullptr);
     hipLaunchKernelGGL(pack_scan_kernel<true>, dim3(nb ? nb : 1), dim3(1024), 0, c.stream, ws.hist, n_order, ws.glist_order,
-                       ws.list_start, ws.tile_base, ws.stile_base, ws.score_base, ws.step_dev, ws.tile_counter, hdr,
+                       ws.list_start, ws.tile_base, ws.stile_base, ws.step_dev, ws.tile_counter, hdr,
                        ws.pack_tot, ws.step_host);
     if (grid_items)
         hipLaunchKernelGGL(pack_scatter_kernel, dim3((grid_items + 255) / 256), dim3(256), 0, c.stream, hdr,
-                           ws.item_glist, ws.item_slot, ws.item_rank, ws.list_start, ws.score_base, ws.glist_len,
-                           ws.sorted_slot, ws.item_score_off, ws.item_sorted_pos);
+                           ws.item_glist, ws.item_slot, ws.item_rank, ws.list_start, ws.sorted_slot, ws.item_sorted_pos);
     hipLaunchKernelGGL(pack_tiles_kernel, dim3((total_lists + 255) / 256), dim3(256), 0, c.stream, total_lists,
-                       ws.hist, ws.list_start, ws.tile_base, ws.stile_base, ws.score_base, ws.glist_len, ws.glist_voff,
+                       ws.hist, ws.list_start, ws.tile_base, ws.stile_base, ws.glist_len, ws.glist_voff,
                        ws.glist_index, ws.indexes, hdr, ws.tiles, ws.stiles);
     return hipGetLastError();
 }

@@ -21,8 +21,11 @@
 //  * main launch (FILTER = true): every other vector is scored (the sample was the first two blocks of
 //    each list; what passed of it already heads the candidate regions, put there by the threshold
 //    kernel), and only the scores not worse than the query's threshold are appended, as (score bits,
-//    position in list) pairs, to the (query, chunk) region of the candidate buffer.  The result is
-//    exact; the threshold only decides how much is written (about k / sample size of the scores).
+//    stored position of the vector) pairs, to the query's region of the candidate buffer: one region per
+//    running query and step, sized by the step's plan from what the filter is expected to let through, with
+//    a counter that keeps counting when the region is full -- the merge kernel then sees that pairs are
+//    missing and scores that query's lists again itself.  The result is exact either way; the threshold
+//    only decides how much is written (about k / sample size of the scores).
 //
 // Two kernels:
 //  * scan_wave_kernel (rows of 512 / 1024 / 1536 bytes): ONE WAVEFRONT PER TILE, no barriers.  The wavefront keeps the tile's 32 query rows in registers as MFMA operands (one
@@ -88,45 +91,24 @@ __device__ __forceinline__ void scan_store_block(const tri_f32x16 &acc, float vn
     }
 }
 
-// Filtering epilogue of one 32-vector block: a score enters the candidate list of its query only if
-// its key is not above the query's threshold.  thr / cnt: LDS arrays indexed by the query's row in the
-// tile; a passing lane takes the next free pair of its query's region with an LDS atomic (the order
-// inside a region carries no meaning).
-typedef unsigned int scan_u32x2 __attribute__((ext_vector_type(2)));
-
-__device__ __forceinline__ void scan_filter_block(const tri_f32x16 &acc, float vn, const float (&qn)[16],
-                                                  uint32_t l2mask, const uint32_t *thr, uint32_t *cnt, uint32_t kg,
-                                                  uint32_t nq, bool vec_ok, uint32_t list_pos,
-                                                  __amdgpu_buffer_rsrc_t ors, uint32_t pitch_bytes)
-{
-#pragma unroll
-    for (int i = 0; i < 16; ++i) {
-        const uint32_t j = 8 * (i / 4) + 4 * kg + (i % 4);
-        const bool is_l2 = (l2mask >> i) & 1u;
-        const float v = is_l2 ? (vn + qn[i]) - 2.0f * acc[i] : acc[i];
-        const uint32_t key = tri_score_key(v, is_l2 ? 0u : 1u);
-        if (vec_ok && j < nq && key <= thr[j]) {
-            const uint32_t pos = atomicAdd(&cnt[j], 1u);
-            const scan_u32x2 pair = {__float_as_uint(v), list_pos};
-            __builtin_amdgcn_raw_buffer_store_b64(pair, ors, j * pitch_bytes + pos * 8u, 0, 0);
-        }
-    }
-}
-
-// The same for the one-wavefront-per-tile kernel.  A store instruction that really writes is costly in
-// the middle of the stream (vector-memory operations of a wavefront retire in order, so every later
-// wait for a prefetched group also waits for the store's acknowledgement from memory), while a block
-// yields only a few dozen candidates.  So candidates are first staged in a wavefront-private LDS
-// array -- no branches, no vector-memory traffic: a ballot gives each passing lane its place, lanes
-// that did not pass write to a per-lane dump entry behind the array -- and leave for the candidate
-// buffer in a burst when the array could not take another full block, or when the tile ends.
-//   entry = (score bits, query row in the tile << 27 | position in the list); positions are below
+// Candidates of a tile are first staged in LDS -- a store instruction that really writes is costly in the
+// middle of the stream (vector-memory operations of a wavefront retire in order, so every later wait for a
+// prefetched group also waits for the store's acknowledgement from memory), while a block yields only a few
+// dozen candidates -- and leave for the queries' regions in a burst when the array could not take another full
+// block, or when the tile ends.
+//   entry = (score bits, query row in the tile << 27 | position in the tile's chunk); positions are below
 //   2^24 (a list is shorter than 2^31 bytes, a row at least 128).
-#define SCAN_STAGE_CAP 4096u            // entries (8 bytes each); a block adds at most TRI_QT * TRI_VB = 1024
+// A burst: count the staged entries per query (LDS), reserve that many pairs in each query's region with ONE
+// global atomic per query -- the counter keeps counting past the region's capacity, which is how the merge kernel
+// learns that pairs were dropped --, then write the pairs that fit.  The order inside a region carries no meaning.
+#define SCAN_STAGE_CAP 4096u            // entries (8 bytes each) of a wavefront's array; a block adds at most TRI_QT * TRI_VB = 1024
+#define SCAN_LSTAGE_CAP 3072u           // entries of the array the four wavefronts of the LDS kernel share
 
+// One-wavefront-per-tile kernel: no branches, no vector-memory traffic while staging -- a ballot gives each passing
+// lane its place, lanes that did not pass write to a per-lane dump entry behind the array.
 __device__ __forceinline__ void scan_stage_block(const tri_f32x16 &acc, float vn, const float (&qn)[16],
                                                  uint32_t l2mask, const uint32_t (&thr)[16], uint32_t kg, uint32_t lane,
-                                                 uint32_t nq, bool vec_ok, uint32_t list_pos, uint2 *stage,
+                                                 uint32_t nq, bool vec_ok, uint32_t chunk_pos, uint2 *stage,
                                                  uint32_t &stage_n)
 {
 #pragma unroll
@@ -138,23 +120,34 @@ __device__ __forceinline__ void scan_stage_block(const tri_f32x16 &acc, float vn
         const bool pass = vec_ok && j < nq && key <= thr[i];
         const uint64_t m = __ballot(pass);
         const uint32_t before = __builtin_amdgcn_mbcnt_hi((uint32_t)(m >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)m, 0u));
-        stage[pass ? stage_n + before : SCAN_STAGE_CAP + lane] = make_uint2(__float_as_uint(v), (j << 27) | list_pos);
+        stage[pass ? stage_n + before : SCAN_STAGE_CAP + lane] = make_uint2(__float_as_uint(v), (j << 27) | chunk_pos);
         stage_n += (uint32_t)__popcll(m);
     }
 }
 
-// Burst of the staged candidates into the (query, chunk) regions of the candidate buffer; qcnt[j] = pairs
-// already in the region of the tile's query j (the order inside a region carries no meaning).
-__device__ __forceinline__ void scan_stage_flush(const uint2 *stage, uint32_t &stage_n, uint32_t *qcnt, uint32_t lane,
-                                                 __amdgpu_buffer_rsrc_t ors, uint32_t pitch_bytes)
+// Burst of a wavefront's staged candidates.  qloc / qbase: LDS scratch per query row; qoff / qcap: the queries'
+// regions; slot: this lane's query (lanes below nq); pos_base: stored position of the chunk's first vector.
+__device__ __forceinline__ void scan_stage_flush(const uint2 *stage, uint32_t &stage_n, uint32_t *qloc, uint32_t *qbase,
+                                                 const uint32_t *qoff, const uint32_t *qcap, uint32_t lane, uint32_t nq,
+                                                 uint32_t slot, uint32_t *__restrict__ slot_cand_cnt,
+                                                 uint2 *__restrict__ cand, uint32_t pos_base)
 {
+    __builtin_amdgcn_wave_barrier();
+    if (lane < TRI_QT) qloc[lane] = 0;
+    __builtin_amdgcn_wave_barrier();
+    for (uint32_t e = lane; e < stage_n; e += 64) atomicAdd(&qloc[stage[e].y >> 27], 1u);
+    __builtin_amdgcn_wave_barrier();
+    if (lane < nq) {
+        const uint32_t c = qloc[lane];
+        qbase[lane] = c ? atomicAdd(&slot_cand_cnt[slot], c) : 0u;
+        qloc[lane] = 0;
+    }
     __builtin_amdgcn_wave_barrier();
     for (uint32_t e = lane; e < stage_n; e += 64) {
         const uint2 en = stage[e];
         const uint32_t j = en.y >> 27;
-        const uint32_t q = atomicAdd(&qcnt[j], 1u);
-        const scan_u32x2 pair = {en.x, en.y & 0x07FFFFFFu};
-        __builtin_amdgcn_raw_buffer_store_b64(pair, ors, j * pitch_bytes + q * 8u, 0, 0);
+        const uint32_t pos = qbase[j] + atomicAdd(&qloc[j], 1u);
+        if (pos < qcap[j]) cand[(size_t)qoff[j] + pos] = make_uint2(en.x, pos_base + (en.y & 0x07FFFFFFu));
     }
     __builtin_amdgcn_wave_barrier();
     stage_n = 0;
@@ -169,8 +162,9 @@ __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(1, 1))) void
     const TriTile *__restrict__ tiles, const uint32_t *__restrict__ n_tiles_ptr, uint32_t *__restrict__ tile_counter,
     uint32_t my_class, const uint32_t *__restrict__ sorted_slot, const uint8_t *__restrict__ slot_query,
     uint32_t slot_row_bytes, uint32_t n_slots, const TriSlotMeta *__restrict__ slot_meta,
-    const float *__restrict__ slot_qnorm, const uint32_t *__restrict__ thr_key, uint32_t *__restrict__ surv_count,
-    float *__restrict__ out_buf)
+    const float *__restrict__ slot_qnorm, const uint32_t *__restrict__ thr_key,
+    const uint32_t *__restrict__ slot_cand_off, const uint32_t *__restrict__ slot_cand_cap,
+    uint32_t *__restrict__ slot_cand_cnt, void *__restrict__ out_buf)
 {
     static_assert(NG % RG == 0, "ring slots must line up across blocks");
     constexpr uint32_t row_bytes = NG * 128;
@@ -182,7 +176,7 @@ __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(1, 1))) void
         __builtin_amdgcn_make_buffer_rsrc((void *)slot_query, 0, n_slots * slot_row_bytes, SCAN_BUF_FLAGS);
     // candidate staging of this wavefront (the workgroup IS one wavefront) + 64 dump entries
     __shared__ uint2 stage[FILTER ? SCAN_STAGE_CAP + 64 : 1];
-    __shared__ uint32_t qcnt[TRI_QT];
+    __shared__ uint32_t rg_loc[TRI_QT], rg_base[TRI_QT], rg_off[TRI_QT], rg_cap[TRI_QT];   // the queries' candidate regions
 
     uint32_t t = 0;
     if (lane == 0) t = atomicAdd(tile_counter, 1u);
@@ -233,7 +227,12 @@ __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(1, 1))) void
             const float qn_own = live ? slot_qnorm[slot] : 0.f;
             const bool l2_own = live ? slot_meta[slot].metric == 0u : false;
             const uint32_t thr_own = FILTER && live ? thr_key[slot] : 0u;
-            const uint32_t cnt_own = b0 && live ? surv_count[(tl.item_pos + r) * TRI_TILES_PER_ITEM] : 0u;
+            if constexpr (FILTER) {
+                if (lane < TRI_QT) {
+                    rg_off[lane] = live ? slot_cand_off[slot] : 0u;
+                    rg_cap[lane] = live ? slot_cand_cap[slot] : 0u;
+                }
+            }
             const uint32_t l2_all = (uint32_t)__ballot(l2_own && lane < 32);
             float qn[16];
             uint32_t thr[16];
@@ -246,13 +245,13 @@ __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(1, 1))) void
                 l2mask |= ((l2_all >> j) & 1u) << i;
             }
             uint32_t stage_n = 0;
-            if constexpr (FILTER) qcnt[r] = cnt_own;
             const uint32_t pitch_bytes = tl.pitch * 4u;
-            // output region of the tile: dense rows of nblocks*32 scores, or (query, chunk) pair regions
+            // sample launch: the tile's dense rows of nblocks*32 scores
             const __amdgpu_buffer_rsrc_t ors = __builtin_amdgcn_make_buffer_rsrc(
-                (void *)(out_buf + tl.out_off), 0,
-                ((tl.nq - 1) * tl.pitch + (FILTER ? 2u * len : nblocks * TRI_VB)) * 4u, SCAN_BUF_FLAGS);
+                (void *)((float *)out_buf + (FILTER ? 0 : tl.out_off)), 0,
+                FILTER ? 0u : ((tl.nq - 1) * tl.pitch + nblocks * TRI_VB) * 4u, SCAN_BUF_FLAGS);
             const uint32_t lane_off = 4 * kg * pitch_bytes + r * 4;
+            const uint32_t pos_base = (uint32_t)tl.out_off;     // (main launch: stored position of the chunk's first vector)
             __builtin_amdgcn_sched_barrier(0);
 
             for (uint32_t b = b0; b < nblocks; ++b, off += blk_bytes) {
@@ -278,18 +277,17 @@ __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(1, 1))) void
                 if constexpr (FILTER) {
                     const uint32_t vpos = b * TRI_VB + r;
                     if (stage_n > SCAN_STAGE_CAP - TRI_QT * TRI_VB)     // (uniform, and rare: a few dozen pass per block)
-                        scan_stage_flush(stage, stage_n, qcnt, lane, ors, pitch_bytes);
-                    scan_stage_block(acc, vn, qn, l2mask, thr, kg, lane, tl.nq, vpos < len, tl.vec_begin + vpos, stage,
-                                     stage_n);
+                        scan_stage_flush(stage, stage_n, rg_loc, rg_base, rg_off, rg_cap, lane, tl.nq, slot, slot_cand_cnt,
+                                         (uint2 *)out_buf, pos_base);
+                    scan_stage_block(acc, vn, qn, l2mask, thr, kg, lane, tl.nq, vpos < len, vpos, stage, stage_n);
                 } else {
                     scan_store_block(acc, vn, qn, l2mask, ors, lane_off + b * (TRI_VB * 4u), pitch_bytes, true);
                 }
                 __builtin_amdgcn_sched_barrier(0);
             }
-            if constexpr (FILTER) {
-                scan_stage_flush(stage, stage_n, qcnt, lane, ors, pitch_bytes);
-                if (lane < tl.nq) surv_count[(tl.item_pos + lane) * TRI_TILES_PER_ITEM + tl.chunk] = qcnt[lane];
-            }
+            if constexpr (FILTER)
+                scan_stage_flush(stage, stage_n, rg_loc, rg_base, rg_off, rg_cap, lane, tl.nq, slot, slot_cand_cnt,
+                                 (uint2 *)out_buf, pos_base);
         }
         t = __builtin_amdgcn_readfirstlane(t_next);
     }
@@ -301,9 +299,76 @@ struct ScanShared {
     float qnorm[TRI_QT];
     uint32_t metric[TRI_QT];
     uint32_t thr[TRI_QT];
-    uint32_t cnt[TRI_QT];
+    uint32_t cnt[TRI_QT], base[TRI_QT];     // scratch of the candidate burst
+    uint32_t off[TRI_QT], cap[TRI_QT];      // the queries' regions of the candidate buffer
     uint32_t tile;
+    uint32_t stage_n;                       // entries asked for in the workgroup's staging array
 };
+
+// What the scan kernels get besides the tile: where the candidates go.
+struct ScanOut {
+    uint32_t *slot_cand_cnt;
+    uint2 *cand;
+    uint2 *lstage;          // the LDS kernel's staging array
+    uint32_t pos_base;      // stored position of the chunk's first vector
+};
+
+// Filtering epilogue of one 32-vector block in the LDS kernel: passing scores are appended to the staging array
+// the workgroup's four wavefronts share (one LDS atomic per wavefront and accumulator); should it be full, a
+// candidate goes straight to its query's region, one global atomic each.
+__device__ __forceinline__ void scan_filter_block(const tri_f32x16 &acc, float vn, const float (&qn)[16],
+                                                  uint32_t l2mask, ScanShared &sh, const ScanOut &out, uint32_t kg,
+                                                  uint32_t nq, bool vec_ok, uint32_t chunk_pos)
+{
+    const uint32_t lane = threadIdx.x & 63;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+        const uint32_t j = 8 * (i / 4) + 4 * kg + (i % 4);
+        const bool is_l2 = (l2mask >> i) & 1u;
+        const float v = is_l2 ? (vn + qn[i]) - 2.0f * acc[i] : acc[i];
+        const uint32_t key = tri_score_key(v, is_l2 ? 0u : 1u);
+        const bool pass = vec_ok && j < nq && key <= sh.thr[j];
+        const uint64_t m = __ballot(pass);
+        if (m) {                                               // (uniform across the wavefront)
+            const int leader = __ffsll((unsigned long long)m) - 1;
+            uint32_t first = 0;
+            if ((int)lane == leader) first = atomicAdd(&sh.stage_n, (uint32_t)__popcll(m));
+            first = (uint32_t)__shfl((int)first, leader, 64);
+            const uint32_t idx = first + (uint32_t)__popcll(m & ((1ull << lane) - 1ull));
+            if (pass) {
+                if (idx < SCAN_LSTAGE_CAP) {
+                    out.lstage[idx] = make_uint2(__float_as_uint(v), (j << 27) | chunk_pos);
+                } else {
+                    const uint32_t pos = atomicAdd(&out.slot_cand_cnt[sh.slot[j]], 1u);
+                    if (pos < sh.cap[j]) out.cand[(size_t)sh.off[j] + pos] = make_uint2(__float_as_uint(v), out.pos_base + chunk_pos);
+                }
+            }
+        }
+    }
+}
+
+// Burst of the workgroup's staged candidates at the end of a tile (all threads; barriers inside).
+__device__ __forceinline__ void scan_lds_flush(ScanShared &sh, const ScanOut &out, uint32_t nq)
+{
+    __syncthreads();                        // every wavefront has staged its candidates
+    const uint32_t n = sh.stage_n < SCAN_LSTAGE_CAP ? sh.stage_n : SCAN_LSTAGE_CAP;
+    if (threadIdx.x < TRI_QT) sh.cnt[threadIdx.x] = 0;
+    __syncthreads();
+    for (uint32_t e = threadIdx.x; e < n; e += TRI_SCAN_THREADS) atomicAdd(&sh.cnt[out.lstage[e].y >> 27], 1u);
+    __syncthreads();
+    if (threadIdx.x < nq) {
+        const uint32_t c = sh.cnt[threadIdx.x];
+        sh.base[threadIdx.x] = c ? atomicAdd(&out.slot_cand_cnt[sh.slot[threadIdx.x]], c) : 0u;
+        sh.cnt[threadIdx.x] = 0;
+    }
+    __syncthreads();
+    for (uint32_t e = threadIdx.x; e < n; e += TRI_SCAN_THREADS) {
+        const uint2 en = out.lstage[e];
+        const uint32_t j = en.y >> 27;
+        const uint32_t pos = sh.base[j] + atomicAdd(&sh.cnt[j], 1u);
+        if (pos < sh.cap[j]) out.cand[(size_t)sh.off[j] + pos] = make_uint2(en.x, out.pos_base + (en.y & 0x07FFFFFFu));
+    }
+}
 
 // One tile with a compile-time number NG of 128-byte groups per row (NG % SCAN_RING == 0).  The
 // wavefront's blocks b = wave, wave+4, ... form ONE stream of (block, group) steps: while group g is
@@ -311,7 +376,8 @@ struct ScanShared {
 // one -- are already in flight, so the stream does not drain at block boundaries.
 template <int DT, int NG, bool FILTER>
 __device__ __forceinline__ void scan_tile_pipelined(const TriTile &tl, const uint8_t *__restrict__ qlds,
-                                                    uint32_t pitch, ScanShared &sh, float *__restrict__ out_buf)
+                                                    uint32_t pitch, ScanShared &sh, float *__restrict__ out_buf,
+                                                    const ScanOut &out)
 {
     static_assert(NG % SCAN_RING == 0, "ring slots must line up across blocks");
     const uint32_t lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -333,8 +399,8 @@ __device__ __forceinline__ void scan_tile_pipelined(const TriTile &tl, const uin
         l2mask |= (sh.metric[j] == 0u ? 1u : 0u) << i;
     }
     const uint32_t pitch_bytes = tl.pitch * 4u;
-    const __amdgpu_buffer_rsrc_t ors = __builtin_amdgcn_make_buffer_rsrc(
-        (void *)(out_buf + tl.out_off), 0, ((tl.nq - 1) * tl.pitch + (FILTER ? 2u * len : nblocks * TRI_VB)) * 4u,
+    const __amdgpu_buffer_rsrc_t ors = __builtin_amdgcn_make_buffer_rsrc(       // (sample launch: the tile's dense rows)
+        (void *)(out_buf + (FILTER ? 0 : tl.out_off)), 0, FILTER ? 0u : ((tl.nq - 1) * tl.pitch + nblocks * TRI_VB) * 4u,
         SCAN_BUF_FLAGS);
     const uint32_t lane_off = 4 * kg * pitch_bytes + r * 4;
     constexpr uint32_t bstride = (TRI_SCAN_THREADS / 64) * TRI_VB * row_bytes;   // to the wavefront's next block
@@ -370,8 +436,7 @@ __device__ __forceinline__ void scan_tile_pipelined(const TriTile &tl, const uin
             __builtin_amdgcn_sched_barrier(0);
         }
         if constexpr (FILTER)
-            scan_filter_block(acc, vn, qn, l2mask, sh.thr, sh.cnt, kg, tl.nq, b * TRI_VB + r < len,
-                              tl.vec_begin + b * TRI_VB + r, ors, pitch_bytes);
+            scan_filter_block(acc, vn, qn, l2mask, sh, out, kg, tl.nq, b * TRI_VB + r < len, b * TRI_VB + r);
         else
             scan_store_block(acc, vn, qn, l2mask, ors, lane_off + b * (TRI_VB * 4u), pitch_bytes, true);
         __builtin_amdgcn_sched_barrier(0);
@@ -382,7 +447,7 @@ __device__ __forceinline__ void scan_tile_pipelined(const TriTile &tl, const uin
 // overlap across blocks.
 template <int DT, bool FILTER>
 __device__ __forceinline__ void scan_tile_generic(const TriTile &tl, const uint8_t *__restrict__ qlds, uint32_t pitch,
-                                                  ScanShared &sh, float *__restrict__ out_buf)
+                                                  ScanShared &sh, float *__restrict__ out_buf, const ScanOut &out)
 {
     const uint32_t lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const uint32_t r = lane & 31, kg = lane >> 5;
@@ -404,8 +469,8 @@ __device__ __forceinline__ void scan_tile_generic(const TriTile &tl, const uint8
         l2mask |= (sh.metric[j] == 0u ? 1u : 0u) << i;
     }
     const uint32_t pitch_bytes = tl.pitch * 4u;
-    const __amdgpu_buffer_rsrc_t ors = __builtin_amdgcn_make_buffer_rsrc(
-        (void *)(out_buf + tl.out_off), 0, ((tl.nq - 1) * tl.pitch + (FILTER ? 2u * len : nblocks * TRI_VB)) * 4u,
+    const __amdgpu_buffer_rsrc_t ors = __builtin_amdgcn_make_buffer_rsrc(       // (sample launch: the tile's dense rows)
+        (void *)(out_buf + (FILTER ? 0 : tl.out_off)), 0, FILTER ? 0u : ((tl.nq - 1) * tl.pitch + nblocks * TRI_VB) * 4u,
         SCAN_BUF_FLAGS);
     const uint32_t lane_off = 4 * kg * pitch_bytes + r * 4;
 
@@ -434,8 +499,7 @@ __device__ __forceinline__ void scan_tile_generic(const TriTile &tl, const uint8
             }
         }
         if constexpr (FILTER)
-            scan_filter_block(acc, vn, qn, l2mask, sh.thr, sh.cnt, kg, tl.nq, b * TRI_VB + r < len,
-                              tl.vec_begin + b * TRI_VB + r, ors, pitch_bytes);
+            scan_filter_block(acc, vn, qn, l2mask, sh, out, kg, tl.nq, b * TRI_VB + r < len, b * TRI_VB + r);
         else
             scan_store_block(acc, vn, qn, l2mask, ors, lane_off + b * (TRI_VB * 4u), pitch_bytes, true);
     }
@@ -446,11 +510,13 @@ __global__ __launch_bounds__(TRI_SCAN_THREADS) __attribute__((amdgpu_waves_per_e
     const TriTile *__restrict__ tiles, const uint32_t *__restrict__ n_tiles_ptr, uint32_t *__restrict__ tile_counter,
     uint32_t my_class, const uint32_t *__restrict__ sorted_slot, const uint8_t *__restrict__ slot_query,
     uint32_t slot_row_bytes, uint32_t n_slots, const TriSlotMeta *__restrict__ slot_meta,
-    const float *__restrict__ slot_qnorm, const uint32_t *__restrict__ thr_key, uint32_t *__restrict__ surv_count,
-    float *__restrict__ out_buf)
+    const float *__restrict__ slot_qnorm, const uint32_t *__restrict__ thr_key,
+    const uint32_t *__restrict__ slot_cand_off, const uint32_t *__restrict__ slot_cand_cap,
+    uint32_t *__restrict__ slot_cand_cnt, void *__restrict__ out_buf)
 {
     extern __shared__ __attribute__((aligned(16))) uint8_t qlds[];
     __shared__ ScanShared sh;
+    __shared__ uint2 lstage[FILTER ? SCAN_LSTAGE_CAP : 1];
     const uint32_t n_tiles = *n_tiles_ptr;
     for (;;) {
         __syncthreads();                        // previous tile's LDS reads are done
@@ -468,8 +534,9 @@ __global__ __launch_bounds__(TRI_SCAN_THREADS) __attribute__((amdgpu_waves_per_e
             sh.qnorm[j] = slot != 0xFFFFFFFFu ? slot_qnorm[slot] : 0.f;
             sh.metric[j] = slot != 0xFFFFFFFFu ? slot_meta[slot].metric : 1u;
             sh.thr[j] = FILTER && slot != 0xFFFFFFFFu ? thr_key[slot] : 0u;
-            // (a list's first chunk counts on from the sample's candidates)
-            sh.cnt[j] = FILTER && tl.vec_begin == 0 && j < tl.nq ? surv_count[(tl.item_pos + j) * TRI_TILES_PER_ITEM] : 0u;
+            sh.off[j] = FILTER && slot != 0xFFFFFFFFu ? slot_cand_off[slot] : 0u;
+            sh.cap[j] = FILTER && slot != 0xFFFFFFFFu ? slot_cand_cap[slot] : 0u;
+            if (j == 0) sh.stage_n = 0;
         }
         __syncthreads();
         // stage the tile's query rows; rows past nq are zero (masked padding)
@@ -482,21 +549,19 @@ __global__ __launch_bounds__(TRI_SCAN_THREADS) __attribute__((amdgpu_waves_per_e
             *(uint4 *)(qlds + j * pitch + c * 16) = v;
         }
         __syncthreads();
+        const ScanOut out = {slot_cand_cnt, (uint2 *)out_buf, lstage, (uint32_t)tl.out_off};
         if constexpr (NG != 0)
-            scan_tile_pipelined<DT, NG, FILTER>(tl, qlds, pitch, sh, out_buf);
+            scan_tile_pipelined<DT, NG, FILTER>(tl, qlds, pitch, sh, (float *)out_buf, out);
         else
-            scan_tile_generic<DT, FILTER>(tl, qlds, pitch, sh, out_buf);
-        if constexpr (FILTER) {
-            __syncthreads();                    // every wavefront has appended its candidates
-            if (threadIdx.x < tl.nq)
-                surv_count[(tl.item_pos + threadIdx.x) * TRI_TILES_PER_ITEM + tl.chunk] = sh.cnt[threadIdx.x];
-        }
+            scan_tile_generic<DT, FILTER>(tl, qlds, pitch, sh, (float *)out_buf, out);
+        if constexpr (FILTER) scan_lds_flush(sh, out, tl.nq);
     }
 }
 
 // ================================================================================ launch
 typedef void (*scan_fn)(const TriTile *, const uint32_t *, uint32_t *, uint32_t, const uint32_t *, const uint8_t *,
-                        uint32_t, uint32_t, const TriSlotMeta *, const float *, const uint32_t *, uint32_t *, float *);
+                        uint32_t, uint32_t, const TriSlotMeta *, const float *, const uint32_t *, const uint32_t *,
+                        const uint32_t *, uint32_t *, void *);
 
 struct ScanVariant {
     scan_fn fn;
@@ -559,7 +624,7 @@ hipError_t tri_launch_scan(const TriLaunchCtx &c, const TriDevWs &ws, uint32_t m
 {
     const TriTile *tiles = sample ? ws.stiles : ws.tiles;
     const uint32_t *n_ptr = sample ? &ws.step_dev->n_sample_tiles : &ws.step_dev->n_tiles;
-    float *out = sample ? ws.sample_scores : ws.scores;
+    void *out = sample ? (void *)ws.sample_scores : (void *)ws.cand;
     for (uint32_t k = 0; k < TRI_SCAN_CLASSES; ++k) {
         if (!(class_mask & (1u << k))) continue;
         const ScanVariant v = sample ? scan_variant<false>(k) : scan_variant<true>(k);
@@ -568,16 +633,16 @@ hipError_t tri_launch_scan(const TriLaunchCtx &c, const TriDevWs &ws, uint32_t m
             // one wavefront per SIMD: 4 per compute unit
             hipLaunchKernelGGL(v.fn, dim3(c.n_cu * 4), dim3(64), 0, c.stream, tiles, n_ptr, counter, k, ws.sorted_slot,
                                ws.slot_query, c.slot_row_bytes, c.S, ws.slot_meta, ws.slot_qnorm, ws.thr_key,
-                               ws.surv_count, out);
+                               ws.slot_cand_off, ws.slot_cand_cap, ws.slot_cand_cnt, out);
         } else {
             const uint32_t lds = scan_lds_bytes(max_row_bytes);
-            uint32_t per_cu = (160u * 1024u - 1024u) / (lds + 1024u);
+            uint32_t per_cu = (160u * 1024u - 1024u) / (lds + 1024u + (sample ? 0u : SCAN_LSTAGE_CAP * 8u));
             per_cu = per_cu < 1 ? 1 : (per_cu > 3 ? 3 : per_cu);
             const hipError_t e = scan_raise_lds(v, (sample ? TRI_SCAN_CLASSES : 0) + k, lds);
             if (e != hipSuccess) return e;
             hipLaunchKernelGGL(v.fn, dim3(c.n_cu * per_cu), dim3(TRI_SCAN_THREADS), lds, c.stream, tiles, n_ptr, counter,
                                k, ws.sorted_slot, ws.slot_query, c.slot_row_bytes, c.S, ws.slot_meta, ws.slot_qnorm,
-                               ws.thr_key, ws.surv_count, out);
+                               ws.thr_key, ws.slot_cand_off, ws.slot_cand_cap, ws.slot_cand_cnt, out);
         }
     }
     return hipGetLastError();

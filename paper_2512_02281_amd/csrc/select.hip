@@ -21,10 +21,15 @@
 //    pass collects those not worse than it.  Whatever the sample says, the result is exact whenever the
 //    pass collected between k and SEL_CAP candidates: the k best of the collected set are then the k
 //    best of all.
+//  * a query whose region of the candidate buffer was too small for what the scan's filter let through (the
+//    region is sized by expectation, the counter says how much was asked for): its candidates are then ALL
+//    vectors of the lists it scanned in this step, scored again here, by the same contraction in the same order
+//    as in the scan kernels (so every score has the same bits), and enumerated as often as the selection needs.
 //  * otherwise (heavy ties, adversarial order): three histogram passes (11 + 11 + 10 bits) find
 //    the key T of the k-th best element; if more elements equal T than are still needed, three more
 //    passes over the ids of those elements find the largest id to keep; one pass gathers exactly k.
 #include "tri_common.h"
+#include "tri_mfma.h"
 
 #define SEL_BINS 2048
 #define SEL_SEGCACHE 544   // pair-segment descriptors cached in LDS (128 lists x 4 chunks, and some)
@@ -48,6 +53,19 @@ struct SelSeg {
     uint32_t pfx;      // len summed over this and all earlier segments (cached descriptors only)
 };
 
+// Candidates that are not stored but scored on demand: every vector of `take` inverted lists of one index
+// against one query row.
+struct SelRescan {
+    const uint32_t *item_glist;   // the lists: item_glist[item_base .. item_base + take)
+    const uint32_t *glist_len, *glist_voff;
+    const TriIndexDev *ix;
+    const uint8_t *qrow;          // the query's padded row
+    float qnorm;
+    uint32_t is_l2;
+    uint32_t item_base, take;
+    uint32_t total;               // vectors in those lists
+};
+
 struct SelSrc {
     const uint2 *cand;
     const uint32_t *ids;
@@ -55,6 +73,7 @@ struct SelSrc {
     const uint32_t *dense_ids;
     uint32_t nps;
     uint32_t dense_len;
+    const SelRescan *rescan;      // or NULL
 };
 
 struct SelShared {
@@ -66,7 +85,7 @@ struct SelShared {
     SelSeg seg[SEL_SEGCACHE];
     uint32_t wave_tot[8];
     uint32_t wmin[TRI_SEL_THREADS / 64], wmax[TRI_SEL_THREADS / 64];
-    uint32_t digit, need, count, cnt, tmax, total_pairs;
+    uint32_t digit, need, count, cnt, tmax, tmin, total_pairs;
 };
 
 __device__ __forceinline__ uint32_t sel_id(const SelSrc &src, uint32_t idx, bool pair)
@@ -153,6 +172,54 @@ __device__ __forceinline__ void sel_cache_segments(SelShared &sh, uint32_t nps, 
     __syncthreads();
 }
 
+// Scores of 32 stored vectors (v0 .. v0 + 31 of a list that starts at `list`) against the query, by one wavefront:
+// the query's pieces as the first operand of every product (all 32 rows of that operand are the query), the
+// vectors' as the second, 128-byte group after group and 32-byte chunk after chunk -- the order in which the scan
+// kernels accumulate, so the sums come out bit for bit the same.  Lane l returns the score of vector v0 + l % 32.
+template <int DT>
+__device__ __forceinline__ float sel_rescan_block(const SelRescan &rs, const uint8_t *__restrict__ list, uint32_t v0, uint32_t len,
+                                                  uint32_t lane)
+{
+    const uint32_t r = lane & 31, kg = lane >> 5;
+    const uint32_t row_bytes = rs.ix->row_bytes;
+    const uint32_t v = v0 + r < len ? v0 + r : len - 1;                  // (rows past the end: any valid row, never used)
+    const uint8_t *x = list + (size_t)v * row_bytes + kg * 16;
+    const uint8_t *q = rs.qrow + kg * 16;
+    tri_f32x16 acc;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) acc[i] = 0.f;
+    for (uint32_t g = 0; g < row_bytes; g += 128)
+#pragma unroll
+        for (int c = 0; c < 4; ++c) tri_mma32<DT>(acc, *(const uint4 *)(q + g + c * 32), *(const uint4 *)(x + g + c * 32));
+    return acc[0];
+}
+
+// f(valid, key, stored position, true) for every stride-th 32-vector block of the lists of rs, uniformly by all
+// 64 lanes; the blocks are dealt round-robin to the workgroup's wavefronts.
+template <class Fn>
+__device__ __forceinline__ void sel_rescan_for_each(const SelRescan &rs, uint32_t desc, uint32_t stride, Fn f)
+{
+    const uint32_t lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    constexpr uint32_t NW = TRI_SEL_THREADS / 64;
+    const uint32_t row_bytes = rs.ix->row_bytes;
+    uint32_t gblock = 0;
+    for (uint32_t it = 0; it < rs.take; ++it) {
+        const uint32_t g = rs.item_glist[rs.item_base + it];
+        const uint32_t len = rs.glist_len[g], voff = rs.glist_voff[g];
+        const uint8_t *list = (const uint8_t *)rs.ix->vecs + (size_t)voff * row_bytes;
+        for (uint32_t v0 = 0; v0 < len; v0 += 32, ++gblock) {
+            if (gblock % stride != 0 || (gblock / stride) % NW != wave) continue;
+            const float dot = rs.ix->dtype == 1u ? sel_rescan_block<TRI_DT_F16>(rs, list, v0, len, lane)
+                                                 : sel_rescan_block<TRI_DT_F32>(rs, list, v0, len, lane);
+            const uint32_t v = v0 + (lane & 31);
+            const bool valid = lane < 32 && v < len;
+            const float vn = rs.ix->vnorm[voff + (valid ? v : v0)];
+            const float score = rs.is_l2 ? (vn + rs.qnorm) - 2.0f * dot : dot;
+            f(valid, valid ? sel_key(score, desc) : 0xFFFFFFFFu, voff + v, true);
+        }
+    }
+}
+
 // Enumerate candidates with wavefront-uniform control flow: f(valid, key, idx, pair) is called by all
 // 64 lanes together (valid = this lane has an element; idx, pair: what sel_id needs).  Work is cut into
 // chunks of 64 * SEL_UNROLL elements that the wavefronts take round-robin, and the loads of a chunk are
@@ -234,6 +301,7 @@ __device__ __forceinline__ void sel_for_each(const SelShared &sh, const SelSrc &
             }
         }
     }
+    if (src.rescan) sel_rescan_for_each(*src.rescan, desc, stride, f);
 }
 
 // Append slot for every lane with pred set: one LDS atomic per wavefront call, not per lane.
@@ -316,36 +384,63 @@ __device__ __forceinline__ float sel_range(SelShared &sh, uint32_t lo, uint32_t 
 
 // A key T with at least m of the n keys a[0..n) not above it, and few more (a: LDS, n >= m >= 1 keys of
 // which at least m are not the padding value all-ones).  Uses sh.hist.
+// The buckets are linear in the KEY, and keys are bit patterns of floats: roughly logarithmic in the score, and
+// around a score of zero immensely sparse (all the tiny values of either sign lie between -x and +x).  Scores that
+// straddle zero therefore leave the best keys crowded into a handful of buckets, and the largest key of the
+// bucket that holds rank m may admit several times m keys.  So the cut is refined: while the bucket of rank m holds
+// more than a few keys, its own key range is cut into buckets again (each level narrows the range 2048-fold).
 __device__ uint32_t sel_keys_threshold(SelShared &sh, const uint32_t *a, uint32_t n, uint32_t m)
 {
-    uint32_t kmin, lo = 0xFFFFFFFFu, hi = 0u;
-    for (uint32_t i = threadIdx.x; i < n; i += TRI_SEL_THREADS) {
-        const uint32_t key = a[i];
-        if (key != 0xFFFFFFFFu) {
-            lo = key < lo ? key : lo;
-            hi = key > hi ? key : hi;
+    uint32_t range_lo = 0u, range_hi = 0xFFFFFFFEu;      // keys still in play
+    uint32_t need = m, t = 0xFFFFFFFEu;
+    for (int level = 0; level < 3; ++level) {
+        uint32_t kmin, lo = 0xFFFFFFFFu, hi = 0u;
+        for (uint32_t i = threadIdx.x; i < n; i += TRI_SEL_THREADS) {
+            const uint32_t key = a[i];
+            if (key >= range_lo && key <= range_hi) {
+                lo = key < lo ? key : lo;
+                hi = key > hi ? key : hi;
+            }
         }
-    }
-    const float scale = sel_range(sh, lo, hi, kmin);
-    for (uint32_t i = threadIdx.x; i < n; i += TRI_SEL_THREADS) atomicAdd(&sh.hist[sel_bucket(a[i], kmin, scale)], 1u);
-    if (threadIdx.x == 0) sh.tmax = 0u;
-    __syncthreads();
-    sel_find_digit(sh, SEL_BINS, m);
-    const uint32_t B = sh.digit;
-    uint32_t best = 0;
-    for (uint32_t i = threadIdx.x; i < n; i += TRI_SEL_THREADS) {
-        const uint32_t key = a[i];
-        if (sel_bucket(key, kmin, scale) == B && key > best) best = key;
-    }
+        const float scale = sel_range(sh, lo, hi, kmin);
+        for (uint32_t i = threadIdx.x; i < n; i += TRI_SEL_THREADS) {
+            const uint32_t key = a[i];
+            if (key >= range_lo && key <= range_hi) atomicAdd(&sh.hist[sel_bucket(key, kmin, scale)], 1u);
+        }
+        if (threadIdx.x == 0) {
+            sh.tmax = 0u;
+            sh.tmin = 0xFFFFFFFFu;
+        }
+        __syncthreads();
+        sel_find_digit(sh, SEL_BINS, need);
+        const uint32_t B = sh.digit, in_bucket = sh.count, need_in = sh.need;
+        uint32_t best = 0u, least = 0xFFFFFFFFu;
+        for (uint32_t i = threadIdx.x; i < n; i += TRI_SEL_THREADS) {
+            const uint32_t key = a[i];
+            if (key >= range_lo && key <= range_hi && sel_bucket(key, kmin, scale) == B) {
+                best = key > best ? key : best;
+                least = key < least ? key : least;
+            }
+        }
 #pragma unroll
-    for (int d = 32; d > 0; d >>= 1) {
-        const uint32_t b2 = (uint32_t)__shfl_xor((int)best, d, 64);
-        best = b2 > best ? b2 : best;
+        for (int d = 32; d > 0; d >>= 1) {
+            const uint32_t b2 = (uint32_t)__shfl_xor((int)best, d, 64), l2 = (uint32_t)__shfl_xor((int)least, d, 64);
+            best = b2 > best ? b2 : best;
+            least = l2 < least ? l2 : least;
+        }
+        if ((threadIdx.x & 63) == 0) {
+            atomicMax(&sh.tmax, best);
+            atomicMin(&sh.tmin, least);
+        }
+        __syncthreads();
+        t = sh.tmax;
+        const uint32_t t_lo = sh.tmin;
+        __syncthreads();                 // (sh.tmax, sh.tmin and the histogram may be reused right away)
+        if (in_bucket <= need_in + 4u || t_lo == t) break;      // the bucket admits at most a few keys beyond rank m, or holds equal keys only
+        range_lo = t_lo;
+        range_hi = t;
+        need = need_in;
     }
-    if ((threadIdx.x & 63) == 0) atomicMax(&sh.tmax, best);
-    __syncthreads();
-    const uint32_t t = sh.tmax;
-    __syncthreads();                     // (sh.tmax and the histogram may be reused right away)
     return t;
 }
 
@@ -485,7 +580,7 @@ __device__ const uint64_t *sel_block_topk(SelShared &sh, const SelSrc &src, SegF
 {
     const uint32_t tid = threadIdx.x;
     sel_cache_segments(sh, src.nps, seg_of);
-    const uint32_t total = sh.total_pairs + src.dense_len;
+    const uint32_t total = sh.total_pairs + src.dense_len + (src.rescan ? src.rescan->total : 0u);
     *n_out = total < k ? total : k;
     if (tid == 0) sh.cnt = 0;
     __syncthreads();
@@ -659,7 +754,7 @@ __global__ __launch_bounds__(TRI_SEL_THREADS) void coarse_select_kernel(
             return;                                               // (uniform: c_le comes from shared memory)
         }
     }
-    const SelSrc src = {nullptr, nullptr, row, nullptr, 0u, nlist};
+    const SelSrc src = {nullptr, nullptr, row, nullptr, 0u, nlist, nullptr};
     auto seg_of = [&](uint32_t) { return SelSeg{0u, 0u, 0u, 0u}; };
     uint32_t n;
     const uint64_t *best = sel_block_topk(sh, src, seg_of, d.nprobe, d.metric, &n);
@@ -682,10 +777,10 @@ hipError_t tri_launch_coarse_select(const TriLaunchCtx &c, const TriDevWs &ws, u
 __global__ __launch_bounds__(TRI_SEL_THREADS) void slot_threshold_kernel(
     const uint8_t *__restrict__ upload, const TriSlotMeta *__restrict__ slot_meta,
     const uint32_t *__restrict__ item_glist, const uint32_t *__restrict__ item_sorted_pos,
-    const uint32_t *__restrict__ glist_len, const float *__restrict__ sample_scores,
-    const float *__restrict__ topk_score, const uint32_t *__restrict__ topk_count, uint32_t kmax,
-    uint32_t *__restrict__ thr_key, const uint64_t *__restrict__ item_score_off, float *__restrict__ cand,
-    uint32_t *__restrict__ surv_count)
+    const uint32_t *__restrict__ glist_len, const uint32_t *__restrict__ glist_voff,
+    const float *__restrict__ sample_scores, const float *__restrict__ topk_score,
+    const uint32_t *__restrict__ topk_count, uint32_t kmax, uint32_t *__restrict__ thr_key, uint2 *__restrict__ cand,
+    uint32_t *__restrict__ slot_cand_off, uint32_t *__restrict__ slot_cand_cap, uint32_t *__restrict__ slot_cand_cnt)
 {
     static_assert(TRI_SAMPLE_VECS % TRI_VB == 0 && TRI_VB == 32, "the sample is the first blocks of a list");
     static_assert(TRI_THRESH_ITEMS * TRI_SAMPLE_VECS + TRI_KMAX_POW2 <= 2 * SEL_CAP, "the sample keys must fit the LDS array");
@@ -699,13 +794,12 @@ __global__ __launch_bounds__(TRI_SEL_THREADS) void slot_threshold_kernel(
     const uint32_t nitems = e.take < TRI_THRESH_ITEMS ? e.take : TRI_THRESH_ITEMS;
     uint32_t *keys = (uint32_t *)sh.pool;                  // room for 2 * SEL_CAP keys
     // per item (kept in the segment cache, which this kernel does not use otherwise): .off = its sample
-    // row, .len = how many of its TRI_SAMPLE_VECS scores exist, .id_off = first pair of its candidate region
+    // row, .len = how many of its TRI_SAMPLE_VECS scores exist, .id_off = stored position of its list's first vector
     const uint32_t ncached = e.take < SEL_SEGCACHE ? e.take : SEL_SEGCACHE;
     if (threadIdx.x == 0) sh.cnt = 0;
     for (uint32_t s = threadIdx.x; s < ncached; s += TRI_SEL_THREADS) {
-        const uint32_t it = e.item_base + s;
-        sh.seg[s] = SelSeg{item_sorted_pos[it], min(glist_len[item_glist[it]], (uint32_t)TRI_SAMPLE_VECS),
-                           (uint32_t)(item_score_off[it] / 2u), 0u};
+        const uint32_t it = e.item_base + s, g = item_glist[it];
+        sh.seg[s] = SelSeg{item_sorted_pos[it], min(glist_len[g], (uint32_t)TRI_SAMPLE_VECS), glist_voff[g], 0u};
     }
     __syncthreads();
     // keys[s * TRI_SAMPLE_VECS + l] = key of sample l of item s (all-ones where the list is shorter), then the running top-k
@@ -728,25 +822,28 @@ __global__ __launch_bounds__(TRI_SEL_THREADS) void slot_threshold_kernel(
     __syncthreads();
     uint32_t thr = 0xFFFFFFFFu;
     if (nvalid >= meta.k) thr = sel_keys_threshold(sh, keys, n, meta.k);
-    if (threadIdx.x == 0) thr_key[e.slot] = thr;
+    if (threadIdx.x == 0) {
+        thr_key[e.slot] = thr;
+        sh.count = 0;                     // (the selection above used it; from here on: pairs emitted)
+    }
+    __syncthreads();
     // The sample IS the first block(s) of every list: its scores that pass the threshold become the first
-    // candidates of their (query, list) item here, and the scan starts behind them.  One item per
-    // half-wavefront; (score bits, position) pairs at the head of the item's region, their number in the
-    // item's first counter (the scan counts on from there).
+    // candidates of the query's region here, and the scan starts every list behind them.  One item per
+    // half-wavefront; (score bits, stored position) pairs, placed through one LDS counter; the main launch counts
+    // on from what this leaves in the slot's counter.
     // (The first TRI_THRESH_ITEMS items' keys are still in LDS -- a key gives back its score bit for bit --;
     // items beyond them, and beyond the cached descriptors, are read again.)
     const uint32_t l32 = threadIdx.x & 31;
     for (uint32_t s = threadIdx.x >> 5; s < e.take; s += TRI_SEL_THREADS / 32) {
-        uint32_t row, n_l, first_pair;
+        uint32_t row, n_l, voff;
         if (s < ncached) {
-            row = sh.seg[s].off; n_l = sh.seg[s].len; first_pair = sh.seg[s].id_off;
+            row = sh.seg[s].off; n_l = sh.seg[s].len; voff = sh.seg[s].id_off;
         } else {
-            const uint32_t it = e.item_base + s;
+            const uint32_t it = e.item_base + s, g = item_glist[it];
             row = item_sorted_pos[it];
-            n_l = min(glist_len[item_glist[it]], (uint32_t)TRI_SAMPLE_VECS);
-            first_pair = (uint32_t)(item_score_off[it] / 2u);
+            n_l = min(glist_len[g], (uint32_t)TRI_SAMPLE_VECS);
+            voff = glist_voff[g];
         }
-        uint32_t kept = 0;
 #pragma unroll
         for (uint32_t sb = 0; sb < TRI_SAMPLE_VECS / 32; ++sb) {      // 32 samples at a time
             const uint32_t l = sb * 32 + l32;
@@ -755,10 +852,18 @@ __global__ __launch_bounds__(TRI_SEL_THREADS) void slot_threshold_kernel(
             const bool pass = l < n_l && key <= thr;
             const uint64_t m = __ballot(pass);
             const uint32_t half = (threadIdx.x & 32) ? (uint32_t)(m >> 32) : (uint32_t)m;
-            if (pass) ((uint2 *)cand)[(size_t)first_pair + kept + __popc(half & ((1u << l32) - 1u))] = make_uint2(__float_as_uint(sel_unkey(key, desc)), l);
-            kept += (uint32_t)__popc(half);
+            uint32_t first = 0;
+            if (l32 == 0 && half) first = atomicAdd(&sh.count, (uint32_t)__popc(half));
+            first = (uint32_t)__shfl((int)first, (int)(threadIdx.x & 32), 64);
+            const uint32_t pos = first + __popc(half & ((1u << l32) - 1u));
+            if (pass && pos < e.cand_cap) cand[(size_t)e.cand_off + pos] = make_uint2(__float_as_uint(sel_unkey(key, desc)), voff + l);
         }
-        if (l32 == 0) surv_count[row * TRI_TILES_PER_ITEM] = kept;
+    }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        slot_cand_off[e.slot] = e.cand_off;
+        slot_cand_cap[e.slot] = e.cand_cap;
+        slot_cand_cnt[e.slot] = sh.count;
     }
 }
 
@@ -766,8 +871,8 @@ hipError_t tri_launch_threshold(const TriLaunchCtx &c, const TriDevWs &ws, uint3
 {
     if (grid_plan == 0) return hipSuccess;
     hipLaunchKernelGGL(slot_threshold_kernel, dim3(grid_plan), dim3(TRI_SEL_THREADS), 0, c.stream, ws.upload, ws.slot_meta,
-                       ws.item_glist, ws.item_sorted_pos, ws.glist_len, ws.sample_scores, ws.topk_score, ws.topk_count,
-                       c.kmax, ws.thr_key, ws.item_score_off, ws.scores, ws.surv_count);
+                       ws.item_glist, ws.item_sorted_pos, ws.glist_len, ws.glist_voff, ws.sample_scores, ws.topk_score,
+                       ws.topk_count, c.kmax, ws.thr_key, ws.cand, ws.slot_cand_off, ws.slot_cand_cap, ws.slot_cand_cnt);
     return hipGetLastError();
 }
 
@@ -795,42 +900,48 @@ __device__ __forceinline__ float sel_l2_diff_form(const uint8_t *__restrict__ x,
 }
 
 // ------------------------------------------------------------------------------------------------
-// Slot merge: one workgroup per running slot of the step.  Candidates = the (score, position) pairs
-// the scan kept for the slot's work items of this step, one segment per (item, chunk), + its running
-// top-k.  Output = new running top-k, or -- when the slot retires in this step -- its final result.
+// Slot merge: one workgroup per running slot of the step.  Candidates = the (score, stored position) pairs
+// the scan kept in the slot's region of the candidate buffer in this step + its running top-k.  Should the
+// region have been too small (the slot's counter ran past its capacity), the pairs in it are ignored and the
+// slot's lists of this step are scored again right here (SelRescan): slow, exact, and rare.
+// Output = new running top-k, or -- when the slot retires in this step -- its final result.
 __global__ __launch_bounds__(TRI_SEL_THREADS) void slot_merge_kernel(
     const uint8_t *__restrict__ upload, const TriSlotMeta *__restrict__ slot_meta,
     const TriIndexDev *__restrict__ indexes, const uint32_t *__restrict__ item_glist,
-    const uint64_t *__restrict__ item_score_off, const uint32_t *__restrict__ item_sorted_pos,
-    const uint32_t *__restrict__ surv_count, const uint32_t *__restrict__ glist_len,
-    const uint32_t *__restrict__ glist_voff, const float *__restrict__ cand, float *__restrict__ topk_score,
+    const uint32_t *__restrict__ slot_cand_cnt, const uint32_t *__restrict__ glist_len,
+    const uint32_t *__restrict__ glist_voff, const uint2 *__restrict__ cand, float *__restrict__ topk_score,
     uint32_t *__restrict__ topk_id, uint32_t *__restrict__ topk_count, uint32_t kmax,
     uint32_t *__restrict__ res_block, const uint32_t *__restrict__ probe, uint32_t nprobe_max,
-    uint32_t *__restrict__ res_probes, const uint8_t *__restrict__ slot_query, uint32_t slot_row_bytes)
+    uint32_t *__restrict__ res_probes, const uint8_t *__restrict__ slot_query, uint32_t slot_row_bytes,
+    const float *__restrict__ slot_qnorm, uint32_t *__restrict__ rescans)
 {
     __shared__ SelShared sh;
     const TriStepHdr *hdr = (const TriStepHdr *)upload;
     if (blockIdx.x >= hdr->n_plan) return;
-    const uint32_t min_chunk = hdr->min_chunk;
     const TriPlanEntry e = ((const TriPlanEntry *)(upload + hdr->plan_off))[blockIdx.x];
     const TriSlotMeta meta = slot_meta[e.slot];
     const uint32_t desc = meta.metric == 1u;
     const uint32_t have = e.cursor > 0 ? topk_count[e.slot] : 0u;
     float *run_score = topk_score + (size_t)e.slot * kmax;
     uint32_t *run_id = topk_id + (size_t)e.slot * kmax;
-    const SelSrc src = {(const uint2 *)cand, indexes[meta.index].ids, run_score, run_id,
-                        e.take * TRI_TILES_PER_ITEM, have};
-
-    // pair segment s: chunk s % 4 of item s / 4 (empty when the list has fewer chunks)
-    auto seg_of = [&](uint32_t s) {
-        const uint32_t it = e.item_base + s / TRI_TILES_PER_ITEM, ch = s % TRI_TILES_PER_ITEM;
-        const uint32_t g = item_glist[it];
-        const uint32_t chunk_vecs = tri_chunk_vecs(glist_len[g], min_chunk);
-        const uint32_t nch = (glist_len[g] + chunk_vecs - 1) / chunk_vecs;
-        if (ch >= nch) return SelSeg{0u, 0u, 0u, 0u};
-        return SelSeg{(uint32_t)(item_score_off[it] / 2u) + ch * chunk_vecs,
-                      surv_count[item_sorted_pos[it] * TRI_TILES_PER_ITEM + ch], glist_voff[g], 0u};
-    };
+    const uint32_t asked = slot_cand_cnt[e.slot];
+    const bool overflow = asked > e.cand_cap;                 // (the same for every thread of the workgroup)
+    SelRescan rs = {item_glist, glist_len, glist_voff, &indexes[meta.index], slot_query + (size_t)e.slot * slot_row_bytes,
+                    slot_qnorm[e.slot], meta.metric == 0u, e.item_base, e.take, 0u};
+    if (overflow) {
+        uint32_t part = 0;
+        for (uint32_t it = threadIdx.x; it < e.take; it += TRI_SEL_THREADS) part += glist_len[item_glist[e.item_base + it]];
+        const uint32_t incl = sel_block_scan_incl(part, sh.wave_tot);
+        if (threadIdx.x == TRI_SEL_THREADS - 1) {
+            sh.tmax = incl;
+            atomicAdd(rescans, 1u);
+        }
+        __syncthreads();
+        rs.total = sh.tmax;
+        __syncthreads();
+    }
+    const SelSrc src = {cand, indexes[meta.index].ids, run_score, run_id, overflow ? 0u : 1u, have, overflow ? &rs : nullptr};
+    auto seg_of = [&](uint32_t) { return SelSeg{e.cand_off, asked, 0u, 0u}; };
     uint32_t n;
     const uint64_t *best = sel_block_topk(sh, src, seg_of, meta.k, desc, &n);
     // (all reads of the running buffer are done: sel_block_topk ends with a barrier)
@@ -885,9 +996,9 @@ hipError_t tri_launch_merge(const TriLaunchCtx &c, const TriDevWs &ws, uint32_t 
 {
     if (grid_plan == 0) return hipSuccess;
     hipLaunchKernelGGL(slot_merge_kernel, dim3(grid_plan), dim3(TRI_SEL_THREADS), 0, c.stream, ws.upload, ws.slot_meta,
-                       ws.indexes, ws.item_glist, ws.item_score_off, ws.item_sorted_pos, ws.surv_count,
-                       ws.glist_len, ws.glist_voff, ws.scores, ws.topk_score, ws.topk_id, ws.topk_count, c.kmax,
-                       ws.res_block, ws.probe, c.nprobe_max, keep_probes ? ws.res_probes : (uint32_t *)nullptr,
-                       ws.slot_query, c.slot_row_bytes);
+                       ws.indexes, ws.item_glist, ws.slot_cand_cnt, ws.glist_len, ws.glist_voff, ws.cand, ws.topk_score,
+                       ws.topk_id, ws.topk_count, c.kmax, ws.res_block, ws.probe, c.nprobe_max,
+                       keep_probes ? ws.res_probes : (uint32_t *)nullptr, ws.slot_query, c.slot_row_bytes, ws.slot_qnorm,
+                       ws.rescans);
     return hipGetLastError();
 }

@@ -166,6 +166,7 @@ struct tri_pool {
     StepRec ring[RING];
     uint8_t *pinned = nullptr;         // upload / result blocks of the steps in flight, then the query store
     bool own_pinned = false;           // allocated here (hipHostMalloc) and freed in tri_pool_destroy
+    uint32_t cand_reserve = 0;         // != 0: pairs reserved per query and step instead of the estimate (tri_pool_set_candidate_reserve)
     int static_dev = -1;               // >= 0: the workspace is that device's static array (tri_pool_create_static)
     // a step that failed half-way leaves the slot table out of step with the GPU: the pool is then failed for good
     bool failed = false, inject_failure = false;
@@ -231,22 +232,23 @@ size_t carve(const tri_pool_cfg &c, uint32_t max_row_bytes, uint32_t coarse_rows
     CARVE(item_glist, uint32_t *, W * 4)
     CARVE(item_slot, uint32_t *, W * 4)
     CARVE(item_rank, uint32_t *, W * 4)
-    CARVE(item_score_off, uint64_t *, W * 8)
     CARVE(item_sorted_pos, uint32_t *, W * 4)
     CARVE(sorted_slot, uint32_t *, W * 4)
     CARVE(hist, uint32_t *, G * 4)
     CARVE(list_start, uint32_t *, G * 4)
     CARVE(tile_base, uint32_t *, G * 4)
     CARVE(stile_base, uint32_t *, G * 4)
-    CARVE(score_base, uint64_t *, G * 8)
     CARVE(tiles, TriTile *, (size_t)TRI_TILES_PER_ITEM * W * sizeof(TriTile))
     CARVE(stiles, TriTile *, W * sizeof(TriTile))
     CARVE(tile_counter, uint32_t *, 256)
-    CARVE(surv_count, uint32_t *, (size_t)TRI_TILES_PER_ITEM * W * 4)
     CARVE(sample_scores, float *, W * (size_t)TRI_SAMPLE_VECS * 4)
     CARVE(thr_key, uint32_t *, S * 4)
+    CARVE(slot_cand_off, uint32_t *, S * 4)
+    CARVE(slot_cand_cap, uint32_t *, S * 4)
+    CARVE(slot_cand_cnt, uint32_t *, S * 4)
+    CARVE(rescans, uint32_t *, 256)
     CARVE(step_dev, TriStepDev *, 256)
-    CARVE(scores, float *, (size_t)score_capacity * 4)
+    CARVE(cand, uint2 *, (size_t)score_capacity * 4)
     // (res_block / res_probes point into the pinned host block of the step in flight: set per step)
 #undef CARVE
     return o;
@@ -275,9 +277,11 @@ int derive(const tri_pool_cfg *c, uint32_t *max_row_bytes, uint32_t *coarse_rows
     *coarse_rows = c->coarse_rows ? c->coarse_rows : 1024u;
     if (*coarse_rows > c->slots) *coarse_rows = c->slots;
     *coarse_ldc = round_up(c->max_nlist, 32u);
-    *score_capacity = c->score_capacity ? c->score_capacity : (uint64_t)c->items_per_step * 2048u;
+    // default: room for 1024 kept candidates per slot and 32 per work item (2 words each)
+    *score_capacity = c->score_capacity ? c->score_capacity : 2ull * ((uint64_t)c->slots * 1024u + (uint64_t)c->items_per_step * 32u);
     if (*score_capacity > (1ull << 32))      // candidate pairs are addressed with 32-bit pair numbers
         return tri_fail(TRI_EINVAL, "score_capacity must not exceed 2^32 words");
+    if (*score_capacity < 2ull * c->kmax) return tri_fail(TRI_EINVAL, "score_capacity must hold at least kmax pairs");
     *upload_bytes = sizeof(TriStepHdr) + round_up_sz((size_t)c->slots * sizeof(TriNewDesc), 256) +
                     round_up_sz((size_t)c->slots * sizeof(TriPlanEntry), 256) + (size_t)c->slots * *max_row_bytes;
     return TRI_OK;
@@ -557,6 +561,9 @@ extern "C" int tri_pool_create(const tri_pool_cfg *cfg, void *dev_ws, size_t dev
         if (e != hipSuccess) { delete P; return tri_fail(TRI_EHIP, "hipHostMalloc(%zu) -> %s", L.total, hipGetErrorString(e)); }
         P->own_pinned = true;
     }
+    e = tri_launch_fill_u32(P->stream, P->ws.rescans, 0u, 1);
+    if (e == hipSuccess) e = hipStreamSynchronize(P->stream);
+    if (e != hipSuccess) { tri_pool_destroy(P); return tri_fail(TRI_EHIP, "workspace set-up -> %s", hipGetErrorString(e)); }
     P->qstore = P->pinned + L.qstore_off;
     e = hipHostGetDevicePointer((void **)&P->qstore_dev, P->qstore, 0);
     if (e != hipSuccess) { tri_pool_destroy(P); return tri_fail(TRI_EHIP, "hipHostGetDevicePointer(query store) -> %s", hipGetErrorString(e)); }
@@ -629,7 +636,7 @@ extern "C" int tri_pool_create_static(const tri_pool_cfg *cfg, void *pinned_ws, 
     // before they are read, under counts the step itself produces).  A fill kernel, not a memset.
     TriDevWs lay{};
     carve(*cfg, mrb, cr, ldc, sc, up, (uint8_t *)W.ptr, &lay);
-    const size_t head = (size_t)((uint8_t *)lay.scores - (uint8_t *)W.ptr);
+    const size_t head = (size_t)((uint8_t *)lay.cand - (uint8_t *)W.ptr);
     hipStream_t s = (hipStream_t)cfg->hip_stream;
     HIP_TRY(tri_launch_fill_u32(s, (uint32_t *)W.ptr, 0u, head / 4));
     HIP_TRY(hipStreamSynchronize(s));
@@ -924,8 +931,6 @@ extern "C" int ivf_build(tri_pool *P, const ivf_params *p, const void *base, uin
     for (uint32_t l = 0; l < nlist; ++l) { h_len[l] = h_off[l + 1] - h_off[l]; maxlen = std::max(maxlen, h_len[l]); }
     if ((uint64_t)maxlen * rb >= (1ull << 31))
         return tri_fail(TRI_EINVAL, "longest list (%u vectors of %u bytes) exceeds 2^31 bytes", maxlen, rb);
-    if (2ull * round_up(maxlen, TRI_VB) > P->score_capacity)
-        return tri_fail(TRI_ENOMEM, "longest list (%u) exceeds the pool's score capacity", maxlen);
     tri_index *ix = new (std::nothrow) tri_index();
     if (!ix) return tri_fail(TRI_ENOMEM, "out of host memory");
     ix->pool = P; ix->id = id; ix->p = *p; ix->n = n; ix->dpad = dpad; ix->row_bytes = rb;
@@ -1331,7 +1336,15 @@ int step_locked(tri_pool *P, tri_step_stats *st)
     }
     TriPlanEntry *plan_h = (TriPlanEntry *)(R.up_host + sizeof(TriStepHdr) + desc_bytes);
     uint32_t n_plan = 0, n_items = 0, n_retire = 0;
-    uint64_t score_used = 0;
+    // Every slot of the step gets a region of the candidate buffer for the pairs the scan's filter lets through.
+    // The filter's bound is the k-th best of a sample of 64 vectors per list.  A list of length L is sampled at the
+    // rate 64 / L, so each of the k sample scores under the bound stands for L / 64 vectors of its list: about
+    // k L / 64 vectors pass, with a relative spread of 1 / sqrt(k), and at most that with L the longest list of the
+    // index when all k come from it (long lists are sampled thinnest).  The region holds that with a wide margin,
+    // and everything where the sample cannot give a bound (fewer than k sample scores).  A query that still asks
+    // for more is not wrong, only slow: the merge kernel then scores its lists again itself.
+    const uint64_t cand_pairs = P->score_capacity / 2;
+    uint64_t cand_used = 0;
     R.retire.clear();
     for (uint32_t s : P->order) {
         if (n_items >= cfg.items_per_step) break;
@@ -1339,15 +1352,31 @@ int step_locked(tri_pool *P, tri_step_stats *st)
         const uint32_t remaining = sl.nprobe - sl.cursor;
         uint32_t take = cfg.lists_per_query_step ? std::min(cfg.lists_per_query_step, remaining) : remaining;
         take = std::min(take, cfg.items_per_step - n_items);
-        const uint64_t per_item = 2ull * round_up(sl.index->max_list_len, TRI_VB);   // (score, position) per vector
-        if (per_item) take = (uint32_t)std::min<uint64_t>(take, (P->score_capacity - score_used) / per_item);
         if (take == 0) continue;
+        const Ticket &tk = P->tickets[sl.ticket];
+        const uint64_t everything = (uint64_t)take * round_up(sl.index->max_list_len, TRI_VB);
+        uint64_t want;
+        if (P->cand_reserve) {
+            want = P->cand_reserve;
+        } else if ((uint64_t)tk.k > (uint64_t)take * (TRI_SAMPLE_VECS / 2)) {
+            want = everything;                                      // (no bound from so small a sample)
+        } else {
+            const double per_sample = std::max(1.0, (double)sl.index->max_list_len / TRI_SAMPLE_VECS);
+            want = (uint64_t)(((double)tk.k + 6.0 * std::sqrt((double)tk.k) + 12.0) * per_sample) + 64;
+        }
+        want = std::min<uint64_t>(std::min(want, everything), 0xFFFFFFFFull);
+        const uint64_t room = cand_pairs - cand_used;
+        if (want > room) {
+            if (n_plan > 0 && room < want / 2) continue;            // (it waits for the next step; the first slot of a step always runs)
+            want = room;
+        }
         TriPlanEntry &e = plan_h[n_plan++];
         e.slot = s; e.cursor = sl.cursor; e.take = take; e.item_base = n_items; e.pad_ = 0;
+        e.cand_off = (uint32_t)cand_used; e.cand_cap = (uint32_t)want;
         e.retire_idx = sl.cursor + take == sl.nprobe ? (int32_t)n_retire++ : -1;
         if (e.retire_idx >= 0) R.retire.push_back(sl.ticket);
         n_items += take;
-        score_used += (uint64_t)take * per_item;
+        cand_used += want;
     }
     stats.step = P->step_seq;
     stats.admitted = n_new;
@@ -1822,6 +1851,26 @@ extern "C" int tri_pool_set_replay(tri_pool *P, int on)
     if (on && !P->stream) return tri_fail(TRI_EINVAL, "a step cannot be recorded on the default stream: give the pool a stream of its own");
     std::lock_guard<std::mutex> lk(P->mu);
     P->cfg.flags = on ? (P->cfg.flags | TRI_FLAG_GRAPH) : (P->cfg.flags & ~(uint32_t)TRI_FLAG_GRAPH);
+    return TRI_OK;
+}
+
+extern "C" int tri_pool_set_candidate_reserve(tri_pool *P, uint32_t pairs)
+{
+    if (!P) return tri_fail(TRI_EINVAL, "pool is NULL");
+    std::lock_guard<std::mutex> lk(P->mu);
+    P->cand_reserve = pairs;
+    return TRI_OK;
+}
+
+extern "C" int tri_pool_candidate_rescans(tri_pool *P, uint64_t *rescans)
+{
+    if (!P || !rescans) return tri_fail(TRI_EINVAL, "NULL argument");
+    std::lock_guard<std::mutex> lk(P->mu);
+    HIP_TRY(hipSetDevice(P->device));
+    HIP_TRY(hipStreamSynchronize(P->stream));
+    uint32_t v = 0;
+    HIP_TRY(hipMemcpy(&v, P->ws.rescans, 4, hipMemcpyDeviceToHost));
+    *rescans = v;
     return TRI_OK;
 }
 

@@ -50,6 +50,8 @@ struct TriPlanEntry {
     uint32_t take;       // lists scanned in this step
     uint32_t item_base;  // first work item of this slot in the unsorted item array
     int32_t retire_idx;  // >= 0: the slot finishes in this step, result goes to this record
+    uint32_t cand_cap;   // pairs its region of the candidate buffer holds in this step
+    uint32_t cand_off;   // first pair of that region
     uint32_t pad_;
 };
 
@@ -78,18 +80,19 @@ static_assert(sizeof(TriStepHdr) == 1024, "header is 1024 bytes");
 
 // One scan tile: up to TRI_QT queries against one chunk (all of it, for short lists) of one inverted
 // list.  Self-contained: the scan kernels read nothing else about the list.  Two kinds share the layout:
-//  * main tiles: every vector of the chunk is scored, the scores that pass the query's threshold are
-//    appended as (score bits, position in list) pairs to the (query, chunk) region of the candidate buffer;
+//  * main tiles: every vector of the chunk is scored; the scores that pass a query's threshold are appended
+//    as (score bits, stored position of the vector in its index) pairs to THAT QUERY's region of the
+//    candidate buffer (one region per running query and step, sized by the step's plan);
 //  * sample tiles: only the first TRI_SAMPLE_VECS vectors of the list, all scores written densely.
 struct TriTile {
     uint64_t vec_addr;    // device address of the first vector
     uint64_t vnorm_addr;  // device address of its |x|^2
-    uint64_t out_off;     // 4-byte-word offset of query 0's output region (main: in the candidate buffer, its
-                          // chunk part; sample: in the sample buffer); query j at + j * pitch
+    uint64_t out_off;     // sample tiles: 4-byte-word offset of query 0's row in the sample buffer (query j at
+                          // + j * pitch); main tiles: stored position (in its index) of the tile's first vector
     uint32_t item_pos;    // first of the tile's queries in the list-sorted item array
     uint32_t nq;          // 1..TRI_QT real queries
     uint32_t vec_count;   // vectors to score
-    uint32_t pitch;       // words between the regions of consecutive queries
+    uint32_t pitch;       // sample tiles: words between the rows of consecutive queries
     uint32_t klass;       // which scan kernel serves it (tri_scan_class)
     uint32_t row_bytes;
     uint32_t vec_begin;   // position of the first vector inside its list
@@ -155,22 +158,23 @@ struct TriDevWs {
     uint32_t *item_glist;     // [W]
     uint32_t *item_slot;      // [W]
     uint32_t *item_rank;      // [W]
-    uint64_t *item_score_off; // [W] word offset of the item's region in the candidate buffer
     uint32_t *item_sorted_pos;// [W] position of the item in the list-sorted order
     uint32_t *sorted_slot;    // [W]
     uint32_t *hist;           // [max_total_lists+1]
     uint32_t *list_start;     // [max_total_lists+1]
     uint32_t *tile_base;      // [max_total_lists+1]
     uint32_t *stile_base;     // [max_total_lists+1] first sample tile of each list
-    uint64_t *score_base;     // [max_total_lists+1]
     TriTile *tiles;           // [TRI_TILES_PER_ITEM * W]
     TriTile *stiles;          // [W] sample tiles
     uint32_t *tile_counter;   // [2 * TRI_SCAN_CLASSES] work-queue heads of the scan kernels (main, sample)
-    uint32_t *surv_count;     // [W * TRI_TILES_PER_ITEM] candidates kept per (item, chunk)
     float *sample_scores;     // [W * TRI_SAMPLE_VECS]
     uint32_t *thr_key;        // [S] per slot: keys above this cannot reach its top-k
+    uint32_t *slot_cand_off;  // [S] this step's region of the slot in the candidate buffer: first pair,
+    uint32_t *slot_cand_cap;  // [S]   pairs it holds,
+    uint32_t *slot_cand_cnt;  // [S]   pairs asked for so far (beyond cap: not stored, the merge then re-scans)
+    uint32_t *rescans;        // [1] slots whose region overflowed and whose lists the merge kernel scored again (since creation)
     TriStepDev *step_dev;     // [1]
-    float *scores;            // [score_capacity] candidate buffer: per item 2 * npad words of (score bits, position) pairs
+    uint2 *cand;              // [score_capacity / 2] candidate buffer: (score bits, stored position) pairs
     // results of retiring slots, compact, per step
     uint32_t *res_block;      // [S][1 + 2*kmax]  n, ids[kmax], score bits[kmax]   (pinned host memory of the step
     uint32_t *res_probes;     // [S][nprobe_max]                                    in flight, as the GPU addresses it)

@@ -192,6 +192,46 @@ def test_l2_distances_of_duplicates_and_near_duplicates(dtype):
         assert rep["checked"] == 90
 
 
+@pytest.mark.parametrize("dtype,dim", [("f16", 768), ("f32", 128), ("f32", 384), ("f16", 320), ("f16", 1024)])
+def test_a_candidate_region_that_is_too_small_costs_time_not_exactness(dtype, dim):
+    """Every query of a step gets a region of the candidate buffer sized by what the scan's filter is expected to
+    let through.  With the reserve forced down to a handful of pairs every query asks for more than it was given, and
+    the merge kernel scores its lists again itself: the results must be the same bit for bit as with the estimated
+    reserve (and as the oracle's), for every kind of scan kernel (register-resident rows of 1536 and 512 bytes, the LDS
+    kernel's pipelined 1536-byte fp32 rows, its generic path, 2048-byte rows), both metrics, several steps per query."""
+    tri = harness.lib()
+    rng = np.random.default_rng(400 + dim)
+    np_dtype = np.float32 if dtype == "f32" else np.float16
+    n, nlist, nq = 12_000, 24, 60
+    centres = rng.normal(0.0, 1.0, size=(nlist, dim))
+    base = (centres[rng.integers(0, nlist, n)] + rng.normal(0.0, 0.6, size=(n, dim))).astype(np_dtype)
+    queries = np.ascontiguousarray((centres[rng.integers(0, nlist, nq)] + rng.normal(0.0, 0.6, size=(nq, dim))).astype(np_dtype))
+    k = rng.choice([1, 10, 100, 300], size=nq).astype(np.uint32)
+    nprobe = rng.choice([1, 3, 8], size=nq).astype(np.uint32)
+    metric = rng.integers(0, 2, size=nq).astype(np.uint32)
+    init = base[rng.choice(n, nlist, replace=False)].astype(np.float32)
+    results = {}
+    for reserve in (0, 5):
+        with harness.default_pool(tri, slots=32, lists_per_query_step=3, kmax=512, max_dim=dim, max_nlist=nlist,
+                                  max_total_lists=nlist) as pool:
+            idx = pool.build_index(base, dim, nlist, tri.TRI_F32 if dtype == "f32" else tri.TRI_F16, tri.TRI_L2, 3, centroids=init)
+            tri.tri_pool_set_candidate_reserve(pool.handle, reserve)
+            q = tri.make_queries(idx, queries, k, nprobe, metric)
+            ids, dist, n_out, probes, stats = harness.run_all(tri, pool, q)
+            rescans = tri.tri_pool_candidate_rescans(pool.handle)
+            if reserve == 0:
+                oidx = harness.oracle_index(tri, idx, base)
+                rep = harness.compare_with_oracle(oidx, base, queries, k, nprobe, metric, ids, dist, n_out, probes)
+                assert rep["checked"] == nq
+            results[reserve] = (ids, dist, n_out, rescans, len(stats))
+    _say(f"overflow {dtype} dim {dim}: rescans with the estimated reserve {results[0][3]}, with 5 pairs {results[5][3]} "
+         f"in {results[5][4]} steps")
+    assert results[5][3] > nq / 2 and results[0][3] <= 2
+    assert np.array_equal(results[0][0], results[5][0]), "ids differ when the regions overflow"
+    assert np.array_equal(results[0][1], results[5][1], equal_nan=True), "scores differ when the regions overflow"
+    assert np.array_equal(results[0][2], results[5][2])
+
+
 def test_scheduling_does_not_change_results():
     """Continuous batching must leave results intact: one batch, one list per step, a short task
     array, fewer slots than queries (slot reuse), and mid-stream arrival all give bit-identical
@@ -793,7 +833,7 @@ def test_config4_full_size_in_the_benchmark_configuration():
     Q = cfg.n_queries
     pool = tri.Pool(slots=Q, items_per_step=Q * cfg.nprobe, lists_per_query_step=0, kmax=128, nprobe_max=cfg.nprobe,
                     max_indexes=1, max_total_lists=cfg.nlist, max_nlist=cfg.nlist, max_dim=cfg.dim,
-                    max_outstanding=Q * 2, coarse_rows=0, flags=tri.TRI_FLAG_KEEP_PROBES, score_capacity=(1 << 31))
+                    max_outstanding=Q * 2, coarse_rows=0, flags=tri.TRI_FLAG_KEEP_PROBES, score_capacity=(1 << 27))
     try:
         _say("config 4: build")
         init = base_t[torch.from_numpy(rows).cuda()].float().cpu().numpy()

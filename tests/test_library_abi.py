@@ -85,8 +85,8 @@ def test_workspace_size_and_config_validation(tri):
     small, small_pinned = tri.tri_pool_workspace_bytes(_cfg(tri))
     big, big_pinned = tri.tri_pool_workspace_bytes(_cfg(tri, slots=4096, items_per_step=1 << 18, max_outstanding=8192))
     assert 0 < small < big and small % 256 == 0
-    # the score buffer dominates: W * 1024 floats by default
-    assert big > (1 << 18) * 1024 * 4
+    # the candidate buffer by default: 1024 pairs per slot and 32 per work item, 8 bytes each
+    assert big > (4096 * 1024 + (1 << 18) * 32) * 8
     # pinned host memory: result blocks of the four steps that may be in flight (ids and scores of every slot's
     # kmax results) and a padded row (fp32 rows of max_dim are the widest) per outstanding ticket
     assert small_pinned % 256 == 0 and small_pinned >= 4 * 64 * 2 * 100 * 4 + 256 * 768 * 4
