@@ -231,7 +231,7 @@ __device__ __forceinline__ void sel_rescan_for_each(const SelRescan &rs, uint32_
 //  * the dense array: stride > 1 visits its first ceil(len / stride) elements.
 // (The order of candidates inside the candidate buffer and of the centroids carries no information
 // about scores, which is what makes such subsets usable as samples.)
-template <class SegFn, class Fn>
+template <bool RESCAN, class SegFn, class Fn>
 __device__ __forceinline__ void sel_for_each(const SelShared &sh, const SelSrc &src, SegFn seg_of, uint32_t desc,
                                              uint32_t stride, Fn f)
 {
@@ -301,7 +301,9 @@ __device__ __forceinline__ void sel_for_each(const SelShared &sh, const SelSrc &
             }
         }
     }
-    if (src.rescan) sel_rescan_for_each(*src.rescan, desc, stride, f);
+    if constexpr (RESCAN) {
+        if (src.rescan) sel_rescan_for_each(*src.rescan, desc, stride, f);
+    }
 }
 
 // Append slot for every lane with pred set: one LDS atomic per wavefront call, not per lane.
@@ -358,7 +360,7 @@ __device__ __forceinline__ uint32_t sel_bucket(uint32_t key, uint32_t kmin, floa
 // Bucket range from the smallest and largest key (every thread passes those of its own keys; all-ones,
 // the padding value, must be left out).  Also zeroes the histogram.  Ends with a barrier.  Returns the
 // scale of sel_bucket.
-__device__ __forceinline__ float sel_range(SelShared &sh, uint32_t lo, uint32_t hi, uint32_t &kmin)
+__device__ __forceinline__ float sel_range(SelShared &sh, uint32_t lo, uint32_t hi, uint32_t &kmin, uint32_t *kmax = nullptr)
 {
     const uint32_t lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
 #pragma unroll
@@ -379,6 +381,7 @@ __device__ __forceinline__ float sel_range(SelShared &sh, uint32_t lo, uint32_t 
         hi = sh.wmax[w] > hi ? sh.wmax[w] : hi;
     }
     kmin = lo;
+    if (kmax) *kmax = hi;
     return hi > lo ? ((float)SEL_BINS - 0.01f) / (float)(hi - lo) : 0.f;
 }
 
@@ -402,10 +405,27 @@ __device__ uint32_t sel_keys_threshold(SelShared &sh, const uint32_t *a, uint32_
                 hi = key > hi ? key : hi;
             }
         }
-        const float scale = sel_range(sh, lo, hi, kmin);
+        uint32_t kmax;
+        float scale = sel_range(sh, lo, hi, kmin, &kmax);
+        // (first level: buckets linear in the SCORE -- the float a key stands for, negated for descending order --,
+        // which spreads the keys evenly where scores straddle zero; deeper levels, inside one such bucket: linear in the key)
+        float fmin = 0.f;
+        bool by_value = false;
+        if (level == 0 && kmax > kmin) {
+            fmin = tri_key_score(kmin, 0u);
+            const float span = tri_key_score(kmax, 0u) - fmin;
+            if (span > 0.f && span < 3.0e38f) {
+                by_value = true;
+                scale = ((float)SEL_BINS - 0.01f) / span;
+            }
+        }
+        auto bucket_of = [&](uint32_t key) {
+            return by_value ? (uint32_t)fminf(fmaxf((tri_key_score(key, 0u) - fmin) * scale, 0.f), (float)(SEL_BINS - 1))
+                            : sel_bucket(key, kmin, scale);
+        };
         for (uint32_t i = threadIdx.x; i < n; i += TRI_SEL_THREADS) {
             const uint32_t key = a[i];
-            if (key >= range_lo && key <= range_hi) atomicAdd(&sh.hist[sel_bucket(key, kmin, scale)], 1u);
+            if (key >= range_lo && key <= range_hi) atomicAdd(&sh.hist[bucket_of(key)], 1u);
         }
         if (threadIdx.x == 0) {
             sh.tmax = 0u;
@@ -417,7 +437,7 @@ __device__ uint32_t sel_keys_threshold(SelShared &sh, const uint32_t *a, uint32_
         uint32_t best = 0u, least = 0xFFFFFFFFu;
         for (uint32_t i = threadIdx.x; i < n; i += TRI_SEL_THREADS) {
             const uint32_t key = a[i];
-            if (key >= range_lo && key <= range_hi && sel_bucket(key, kmin, scale) == B) {
+            if (key >= range_lo && key <= range_hi && bucket_of(key) == B) {
                 best = key > best ? key : best;
                 least = key < least ? key : least;
             }
@@ -513,7 +533,7 @@ __device__ const uint64_t *sel_pool_topk(SelShared &sh, uint32_t n, uint32_t k)
 }
 
 // Exact radix select of the k best into sh.pool[0..k), unsorted.  total > k.
-template <class SegFn>
+template <bool RESCAN, class SegFn>
 __device__ void sel_radix(SelShared &sh, const SelSrc &src, SegFn seg_of, uint32_t k, uint32_t desc)
 {
     const uint32_t tid = threadIdx.x;
@@ -525,7 +545,7 @@ __device__ void sel_radix(SelShared &sh, const SelSrc &src, SegFn seg_of, uint32
         for (uint32_t i = tid; i < SEL_BINS; i += TRI_SEL_THREADS) sh.hist[i] = 0;
         __syncthreads();
         const uint32_t hi_shift = shift + width;
-        sel_for_each(sh, src, seg_of, desc, 1u, [&](bool valid, uint32_t key, uint32_t, bool) {
+        sel_for_each<RESCAN>(sh, src, seg_of, desc, 1u, [&](bool valid, uint32_t key, uint32_t, bool) {
             if (valid && (pass == 0 || (key >> hi_shift) == prefix)) atomicAdd(&sh.hist[(key >> shift) & (nb - 1)], 1u);
         });
         __syncthreads();
@@ -544,7 +564,7 @@ __device__ void sel_radix(SelShared &sh, const SelSrc &src, SegFn seg_of, uint32
             for (uint32_t i = tid; i < SEL_BINS; i += TRI_SEL_THREADS) sh.hist[i] = 0;
             __syncthreads();
             const uint32_t hi_shift = shift + width;
-            sel_for_each(sh, src, seg_of, desc, 1u, [&](bool valid, uint32_t key, uint32_t idx, bool pair) {
+            sel_for_each<RESCAN>(sh, src, seg_of, desc, 1u, [&](bool valid, uint32_t key, uint32_t idx, bool pair) {
                 if (!valid || key != T) return;
                 const uint32_t id = sel_id(src, idx, pair);
                 if (pass == 0 || (id >> hi_shift) == idprefix) atomicAdd(&sh.hist[(id >> shift) & (nb - 1)], 1u);
@@ -559,7 +579,7 @@ __device__ void sel_radix(SelShared &sh, const SelSrc &src, SegFn seg_of, uint32
     }
     if (tid == 0) sh.cnt = 0;
     __syncthreads();
-    sel_for_each(sh, src, seg_of, desc, 1u, [&](bool valid, uint32_t key, uint32_t idx, bool pair) {
+    sel_for_each<RESCAN>(sh, src, seg_of, desc, 1u, [&](bool valid, uint32_t key, uint32_t idx, bool pair) {
         bool take = valid && key <= T;
         uint32_t id = 0;
         if (take) {
@@ -574,19 +594,19 @@ __device__ void sel_radix(SelShared &sh, const SelSrc &src, SegFn seg_of, uint32
 
 // Select the k best candidates of src, sorted ascending by (key, id); *n_out = min(k, total).  Returns
 // where they are in LDS.  All threads of the workgroup must call it; it ends with a barrier.
-template <class SegFn>
+template <bool RESCAN, class SegFn>
 __device__ const uint64_t *sel_block_topk(SelShared &sh, const SelSrc &src, SegFn seg_of, uint32_t k, uint32_t desc,
                                           uint32_t *n_out)
 {
     const uint32_t tid = threadIdx.x;
     sel_cache_segments(sh, src.nps, seg_of);
-    const uint32_t total = sh.total_pairs + src.dense_len + (src.rescan ? src.rescan->total : 0u);
+    const uint32_t total = sh.total_pairs + src.dense_len + (RESCAN && src.rescan ? src.rescan->total : 0u);
     *n_out = total < k ? total : k;
     if (tid == 0) sh.cnt = 0;
     __syncthreads();
     if (total <= SEL_CAP) {
         // ---- everything fits
-        sel_for_each(sh, src, seg_of, desc, 1u, [&](bool valid, uint32_t key, uint32_t idx, bool pair) {
+        sel_for_each<RESCAN>(sh, src, seg_of, desc, 1u, [&](bool valid, uint32_t key, uint32_t idx, bool pair) {
             const uint32_t pos = sel_append_pos(valid, &sh.cnt);
             if (valid) sh.pool[pos] = ((uint64_t)key << 32) | sel_id(src, idx, pair);
         });
@@ -596,7 +616,7 @@ __device__ const uint64_t *sel_block_topk(SelShared &sh, const SelSrc &src, SegF
     // ---- threshold from a sample
     uint32_t *skeys = (uint32_t *)sh.pool;
     const uint32_t stride = (total + SEL_SAMPLE - 1) / SEL_SAMPLE;
-    sel_for_each(sh, src, seg_of, desc, stride, [&](bool valid, uint32_t key, uint32_t, bool) {
+    sel_for_each<RESCAN>(sh, src, seg_of, desc, stride, [&](bool valid, uint32_t key, uint32_t, bool) {
         const uint32_t pos = sel_append_pos(valid, &sh.cnt);
         if (valid && pos < 2 * SEL_CAP) skeys[pos] = key;      // (a few sample keys too many are simply dropped)
     });
@@ -611,7 +631,7 @@ __device__ const uint64_t *sel_block_topk(SelShared &sh, const SelSrc &src, SegF
         const uint32_t t0 = sel_keys_threshold(sh, skeys, ns, m + 1);
         if (tid == 0) sh.cnt = 0;
         __syncthreads();
-        sel_for_each(sh, src, seg_of, desc, 1u, [&](bool valid, uint32_t key, uint32_t idx, bool pair) {
+        sel_for_each<RESCAN>(sh, src, seg_of, desc, 1u, [&](bool valid, uint32_t key, uint32_t idx, bool pair) {
             const bool take = valid && key <= t0;
             const uint32_t pos = sel_append_pos(take, &sh.cnt);
             if (take && pos < SEL_CAP) sh.pool[pos] = ((uint64_t)key << 32) | sel_id(src, idx, pair);
@@ -626,7 +646,7 @@ __device__ const uint64_t *sel_block_topk(SelShared &sh, const SelSrc &src, SegF
     __syncthreads();
     if (!done) {
         // ---- exact radix select, then sort the k survivors
-        sel_radix(sh, src, seg_of, k, desc);
+        sel_radix<RESCAN>(sh, src, seg_of, k, desc);
         res = sel_pool_topk(sh, k, k);
     }
     return res;
@@ -757,7 +777,7 @@ __global__ __launch_bounds__(TRI_SEL_THREADS) void coarse_select_kernel(
     const SelSrc src = {nullptr, nullptr, row, nullptr, 0u, nlist, nullptr};
     auto seg_of = [&](uint32_t) { return SelSeg{0u, 0u, 0u, 0u}; };
     uint32_t n;
-    const uint64_t *best = sel_block_topk(sh, src, seg_of, d.nprobe, d.metric, &n);
+    const uint64_t *best = sel_block_topk<false>(sh, src, seg_of, d.nprobe, d.metric, &n);
     for (uint32_t i = tid; i < n; i += TRI_SEL_THREADS) dst[i] = (uint32_t)(best[i] & 0xFFFFFFFFu);
 }
 
@@ -943,7 +963,7 @@ __global__ __launch_bounds__(TRI_SEL_THREADS) void slot_merge_kernel(
     const SelSrc src = {cand, indexes[meta.index].ids, run_score, run_id, overflow ? 0u : 1u, have, overflow ? &rs : nullptr};
     auto seg_of = [&](uint32_t) { return SelSeg{e.cand_off, asked, 0u, 0u}; };
     uint32_t n;
-    const uint64_t *best = sel_block_topk(sh, src, seg_of, meta.k, desc, &n);
+    const uint64_t *best = sel_block_topk<true>(sh, src, seg_of, meta.k, desc, &n);
     // (all reads of the running buffer are done: sel_block_topk ends with a barrier)
     if (e.retire_idx >= 0 && !desc && n > 0) {
         // The scan scores squared L2 in the expanded form |x|^2 + |q|^2 - 2 x.q, whose fp32 error grows with
