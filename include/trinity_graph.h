@@ -38,6 +38,8 @@ typedef struct tri_gpool tri_gpool;   /* one graph index resident on one GPU + t
 
 #define TRI_GRAPH_TOPM_LIMIT 256u     /* largest topM                                                     */
 #define TRI_GRAPH_TASK_LIMIT 256u     /* largest parents * degree, and largest number of entry points      */
+#define TRI_GRAPH_VISITED_HASH 16u     /* tri_graph_cfg.flags                                              */
+#define TRI_GRAPH_VISITED_BITS 32u
 #define TRI_GRAPH_PAD 0xFFFFFFFFu     /* neighbour entries >= n are padding and are skipped                 */
 
 typedef struct {
@@ -52,7 +54,11 @@ typedef struct {
                                   merge of one group runs beside the bandwidth-bound distance launch of
                                   another, and a step is enqueued knowing which of its group's slots the
                                   previous one freed: 1..4 (0 = 2)                                      */
-    uint32_t flags;            /* TRI_FLAG_PROFILE: bracket the step kernel with HIP events              */
+    uint32_t flags;            /* TRI_FLAG_PROFILE: bracket the step kernel with HIP events;
+                                  TRI_GRAPH_VISITED_HASH / TRI_GRAPH_VISITED_BITS: how a request's visited set is kept
+                                  (default: whichever is smaller) -- a hash table of ids sized by what one request
+                                  can see (entry points + max_iters * parents * degree, at most n), or one bit per
+                                  database row; both are exact                                          */
     uint32_t pad_;
     void *hip_stream;          /* stream all work is enqueued on (hipStream_t); NULL = default stream    */
 } tri_graph_cfg;

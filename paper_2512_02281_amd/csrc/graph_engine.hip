@@ -1,7 +1,12 @@
 // The paper's own engine (Sec. 3.2): continuous batching of best-first searches over a fixed-degree
 // neighbour graph, one "extend" of every running request per step.  Per request and on the device: a
-// candidate list topM (sorted composites of score key, id and an "expanded" mark), a visited bit table
-// (one bit per database row, so "first seen" is exact), its query row.  A step is ONE fixed-shape launch
+// candidate list topM (sorted composites of score key, id and an "expanded" mark), a visited set that is
+// exact -- so "first seen" is a property of the ids alone and a trajectory does not depend on timing --, its
+// query row.  The visited set is a hash table of ids sized by what one request can ever see (entry points +
+// max_iters * p * D), whatever the size of the database: a small table that takes the first few thousand ids
+// (a handful of linear probes each), and a large one behind it for ids whose neighbourhood in the small table
+// is taken.  The small tables of all slots together stay cache-resident; a bit per database row and slot, which
+// is used instead where that is the smaller of the two, is a gigabyte at a million rows and 8192 slots.  A step is ONE fixed-shape launch
 // over the slots of a group, a workgroup per slot -- idle slots leave at once, which is the masked padding
 // of the paper's fixed-shape task array -- in three phases:
 //   distance : every task of the slot = one gathered row against the slot's query, 16 lanes per task;
@@ -67,7 +72,11 @@ struct GxDev {           // everything the kernels need, by value
     uint8_t *upload;
     uint64_t n;
     uint32_t dim, dtype, row_pitch, degree, n_seeds;
-    uint32_t S, M, p, T, vwords, max_iters;
+    uint32_t S, M, p, T, max_iters;
+    uint32_t vwords;              // visited set of a slot, in 4-byte words: one bit per row (vcap == 0), or vcap table entries
+    uint32_t vcap, vprim;         // hash mode: entries of the whole table and of the small table at its head (a power of two)
+    uint32_t vprim_shift;         // 32 - log2(vprim)
+    uint32_t *vis_spill;          // [S] hash mode: the slot has ids in the large table (so that one must be cleared at the next admission)
     uint32_t group, ngroups;      // this launch serves the slots s with s % ngroups == group
 };
 
@@ -108,6 +117,42 @@ __global__ void gx_pull_kernel(uint4 *__restrict__ dst, const uint4 *__restrict_
     for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n16; i += stride) dst[i] = src_host[i];
 }
 
+// ------------------------------------------------------------------------------------------ visited
+#define GX_EMPTY 0xFFFFFFFFu
+#define GX_PRIMARY_PROBES 8
+
+// True if id c enters slot s's visited set now, false if it was in it already.  Insert-only, so concurrent calls
+// (also with the same id: exactly one of them gets `true`) need nothing beyond the compare-and-swap.
+__device__ __forceinline__ bool gx_first_seen(const GxDev &D, uint32_t s, uint32_t c)
+{
+    uint32_t *tab = D.visited + (size_t)s * D.vwords;
+    if (D.vcap == 0) {                                     // one bit per database row
+        const uint32_t bit = 1u << (c & 31);
+        return !(atomicOr(&tab[c >> 5], bit) & bit);
+    }
+    const uint32_t h = c * 0x9E3779B1u;
+    uint32_t pos = h >> D.vprim_shift;
+    for (int probe = 0; probe < GX_PRIMARY_PROBES; ++probe) {
+        const uint32_t was = atomicCAS(&tab[pos], GX_EMPTY, c);
+        if (was == GX_EMPTY) return true;
+        if (was == c) return false;
+        pos = (pos + 1) & (D.vprim - 1);
+    }
+    // its neighbourhood in the small table is taken (and stays taken: nothing is ever removed, so a later look-up
+    // of c walks the same way): the large table, which alone has room for every id a request can see
+    uint32_t *sec = tab + D.vprim;
+    const uint32_t nsec = D.vcap - D.vprim;
+    D.vis_spill[s] = 1u;
+    uint32_t p2 = (uint32_t)(((uint64_t)((h ^ (h >> 15)) * 0x85EBCA6Bu) * nsec) >> 32);
+    for (uint32_t probe = 0; probe < nsec; ++probe) {
+        const uint32_t was = atomicCAS(&sec[p2], GX_EMPTY, c);
+        if (was == GX_EMPTY) return true;
+        if (was == c) return false;
+        p2 = p2 + 1 == nsec ? 0u : p2 + 1;
+    }
+    return false;                                          // (not reached: nsec exceeds the ids of one request)
+}
+
 // ------------------------------------------------------------------------------------------ admit
 // One workgroup per admitted query: its zero-padded row and |q|^2 into the slot, visited cleared, topM
 // emptied, the entry points (first-seen only) as the slot's tasks of this step.
@@ -137,7 +182,15 @@ __global__ __launch_bounds__(GX_THREADS) void gx_admit_kernel(GxDev D)
                    ? gx_admit_row<_Float16>((const _Float16 *)d.src_dev, (_Float16 *)qrow, D.dim, D.row_pitch / 2)
                    : gx_admit_row<float>((const float *)d.src_dev, (float *)qrow, D.dim, D.row_pitch / 4);
     uint4 *vis = (uint4 *)(D.visited + (size_t)s * D.vwords);
-    for (uint32_t i = tid; i < D.vwords / 4; i += GX_THREADS) vis[i] = make_uint4(0u, 0u, 0u, 0u);
+    if (D.vcap == 0) {
+        for (uint32_t i = tid; i < D.vwords / 4; i += GX_THREADS) vis[i] = make_uint4(0u, 0u, 0u, 0u);
+    } else {
+        // the small table always; the large one only if the slot's previous request reached it
+        const uint32_t clear = D.vis_spill[s] ? D.vcap : D.vprim;
+        for (uint32_t i = tid; i < clear / 4; i += GX_THREADS) vis[i] = make_uint4(GX_EMPTY, GX_EMPTY, GX_EMPTY, GX_EMPTY);
+        __syncthreads();                                           // (every thread has read the mark)
+        if (tid == 0) D.vis_spill[s] = 0u;
+    }
     for (uint32_t i = tid; i < D.M; i += GX_THREADS) D.topm[(size_t)s * D.M + i] = ~0ull;
     __syncthreads();
     for (uint32_t w = GX_THREADS / 2; w > 0; w >>= 1) {
@@ -148,11 +201,7 @@ __global__ __launch_bounds__(GX_THREADS) void gx_admit_kernel(GxDev D)
     uint32_t v = TRI_GRAPH_PAD;
     if (tid < D.n_seeds) {
         const uint32_t c = D.seeds[tid];
-        if (c < D.n) {
-            const uint32_t bit = 1u << (c & 31);
-            const uint32_t old = atomicOr(&D.visited[(size_t)s * D.vwords + (c >> 5)], bit);
-            if (!(old & bit)) v = c;
-        }
+        if (c < D.n && gx_first_seen(D, s, c)) v = c;
     }
     uint32_t total;
     const uint32_t pos = gx_block_rank(v != TRI_GRAPH_PAD, wave_cnt, &total);
@@ -306,11 +355,7 @@ __device__ __forceinline__ void gx_merge_extend_phase(const GxDev &D, uint32_t s
         const uint32_t par = tid / D.degree, j = tid % D.degree;
         if (par < n_par) {
             const uint32_t c = D.graph[(size_t)parent[par] * D.degree + j];
-            if (c < D.n) {
-                const uint32_t bit = 1u << (c & 31);
-                const uint32_t was = atomicOr(&D.visited[(size_t)s * D.vwords + (c >> 5)], bit);
-                if (!(was & bit)) v = c;
-            }
+            if (c < D.n && gx_first_seen(D, s, c)) v = c;
         }
         const uint32_t pos = gx_block_rank(v != TRI_GRAPH_PAD, wave_cnt, &n_tasks);
         if (v != TRI_GRAPH_PAD) D.tasks[(size_t)s * D.T + pos] = v;
@@ -434,8 +479,8 @@ struct tri_gpool {
 namespace {
 
 struct GLayout {
-    size_t vecs, vnorm, graph, seeds, slot_q, qnorm, meta, topm, visited, tasks, upload, upload_one, total;
-    uint32_t row_pitch, vwords, T;
+    size_t vecs, vnorm, graph, seeds, slot_q, qnorm, meta, topm, visited, vis_spill, tasks, upload, upload_one, total;
+    uint32_t row_pitch, vwords, vcap, vprim, T;
 };
 
 int g_validate(const tri_graph_cfg *c, uint64_t n, uint32_t dim, uint32_t degree, uint32_t dtype)
@@ -447,6 +492,10 @@ int g_validate(const tri_graph_cfg *c, uint64_t n, uint32_t dim, uint32_t degree
         return tri_fail(TRI_EINVAL, "need parents >= 1, degree >= 1 and parents * degree <= %u", TRI_GRAPH_TASK_LIMIT);
     if (c->max_outstanding < c->slots) return tri_fail(TRI_EINVAL, "max_outstanding must be >= slots");
     if (c->groups > GRING) return tri_fail(TRI_EINVAL, "groups must be 0..%u", GRING);
+    if ((c->flags & TRI_GRAPH_VISITED_HASH) && (c->flags & TRI_GRAPH_VISITED_BITS))
+        return tri_fail(TRI_EINVAL, "TRI_GRAPH_VISITED_HASH and TRI_GRAPH_VISITED_BITS exclude each other");
+    if ((uint64_t)c->max_iters * c->parents * degree >= (1ull << 29))
+        return tri_fail(TRI_EINVAL, "max_iters * parents * degree must stay below 2^29");
     if (n == 0 || n >= (1ull << 31)) return tri_fail(TRI_EINVAL, "n must be 1..2^31-1");
     if (dtype != TRI_F32 && dtype != TRI_F16) return tri_fail(TRI_EINVAL, "dtype must be TRI_F32 or TRI_F16");
     if (dim == 0 || gup((size_t)dim * (dtype == TRI_F16 ? 2 : 4), 256) > TRI_MAX_ROW_BYTES)
@@ -458,7 +507,19 @@ GLayout g_layout(const tri_graph_cfg &c, uint64_t n, uint32_t dim, uint32_t degr
 {
     GLayout L{};
     L.row_pitch = (uint32_t)gup((size_t)dim * (dtype == TRI_F16 ? 2 : 4), 256);
-    L.vwords = (uint32_t)gup((n + 31) / 32, 4);
+    // visited set of a slot: a hash table in two parts -- a small one in front (a power of two of at least a quarter
+    // of the ids one request can ever see: its entry points and max_iters extends of p * D neighbours, never more than
+    // n), which takes what a typical request sees, and a large one behind it with room for ALL of those ids at a load
+    // of 0.8 -- or one bit per row where that is smaller (or asked for)
+    const uint32_t bit_words = (uint32_t)gup((n + 31) / 32, 4);
+    const uint64_t ids_seen = std::min<uint64_t>(n, (uint64_t)TRI_GRAPH_TASK_LIMIT + (uint64_t)c.max_iters * c.parents * degree);
+    uint64_t prim = 256;
+    while (prim * 4 < ids_seen) prim <<= 1;
+    const uint64_t cap = prim + gup(ids_seen + ids_seen / 4 + 4, 4);
+    const bool hash = (c.flags & TRI_GRAPH_VISITED_HASH) || (!(c.flags & TRI_GRAPH_VISITED_BITS) && cap < bit_words);
+    L.vcap = hash ? (uint32_t)cap : 0u;
+    L.vprim = hash ? (uint32_t)prim : 0u;
+    L.vwords = hash ? L.vcap : bit_words;
     L.T = TRI_GRAPH_TASK_LIMIT;
     size_t o = 0;
     auto take = [&](size_t bytes) { size_t at = o; o = gup(o + bytes, 256); return at; };
@@ -471,7 +532,8 @@ GLayout g_layout(const tri_graph_cfg &c, uint64_t n, uint32_t dim, uint32_t degr
     L.qnorm = take(S * 4);
     L.meta = take(S * sizeof(GxMeta));
     L.topm = take(S * c.topm * 8);
-    L.visited = take(S * L.vwords * 4);
+    L.visited = take(S * (size_t)L.vwords * 4);
+    L.vis_spill = take(S * 4);
     L.tasks = take(S * L.T * 4);
     L.upload_one = gup(sizeof(GxHdr) + S * sizeof(GxNewDesc), 256);
     L.upload = take(L.upload_one * GRING);
@@ -615,6 +677,9 @@ extern "C" int graph_pool_create(const tri_graph_cfg *cfg, const void *vectors, 
     D.group = 0; D.ngroups = P->ngroups;
     D.n = n; D.dim = dim; D.dtype = dtype; D.row_pitch = L.row_pitch; D.degree = degree; D.n_seeds = n_seeds;
     D.S = cfg->slots; D.M = cfg->topm; D.p = cfg->parents; D.T = L.T; D.vwords = L.vwords; D.max_iters = cfg->max_iters;
+    D.vcap = L.vcap; D.vprim = L.vprim; D.vis_spill = (uint32_t *)(base + L.vis_spill);
+    D.vprim_shift = 32;
+    for (uint32_t v = L.vprim; v > 1; v >>= 1) --D.vprim_shift;
     // index data: rows padded with zeros, neighbour list, entry points, row norms, idle slots
     const size_t es = dtype == TRI_F16 ? 2 : 4;
     hipStream_t s = P->stream;
@@ -623,6 +688,9 @@ extern "C" int graph_pool_create(const tri_graph_cfg *cfg, const void *vectors, 
     if (e == hipSuccess) e = hipMemcpyAsync(base + L.graph, neighbors, n * degree * 4, hipMemcpyDefault, s);
     if (e == hipSuccess) e = hipMemcpyAsync(base + L.seeds, seeds, (size_t)n_seeds * 4, hipMemcpyHostToDevice, s);
     if (e == hipSuccess) e = hipMemsetAsync(base + L.meta, 0, (size_t)cfg->slots * sizeof(GxMeta), s);
+    if (e == hipSuccess) e = hipMemsetAsync(base + L.vis_spill, 0, (size_t)cfg->slots * 4, s);
+    if (e == hipSuccess && L.vcap)      // (hash tables start empty; an admission clears only what its slot's previous request used)
+        e = hipMemsetAsync(base + L.visited, 0xFF, (size_t)cfg->slots * L.vwords * 4, s);
     if (e == hipSuccess) {
         hipLaunchKernelGGL(gx_row_norm_kernel, dim3((unsigned)((n + 3) / 4)), dim3(256), 0, s, D.vecs, D.row_pitch, dtype, n,
                            (float *)(base + L.vnorm));

@@ -16,6 +16,7 @@ GRAPH_EXPORTS = ["graph_pool_bytes", "graph_pool_create", "graph_pool_destroy", 
 TRI_GRAPH_TOPM_LIMIT = 256
 TRI_GRAPH_TASK_LIMIT = 256
 TRI_GRAPH_PAD = 0xFFFFFFFF
+TRI_GRAPH_VISITED_HASH, TRI_GRAPH_VISITED_BITS = 16, 32
 
 
 class tri_graph_cfg(ctypes.Structure):

@@ -14,13 +14,13 @@ import pytest
 
 import graph_inputs
 from oracle import graph_search as gs
-from tests import bruteforce
+from tests import bruteforce, harness
 
 pytestmark = pytest.mark.gpu
 
 
 def _say(msg):
-    print(f"[graph] {msg}", flush=True)
+    harness.say(f"[graph] {msg}")
 
 
 def _lib():
@@ -95,6 +95,48 @@ def test_integer_data_trajectories_equal_the_oracle(np_dtype, dim):
                                                         klass=(np.arange(nq) % 3 == 0).astype(np.uint32))
             assert np.array_equal(ids, ids2) and np.array_equal(dist.view(np.uint32), dist2.view(np.uint32))
             assert np.array_equal(it, it2) and np.array_equal(ev, ev2)
+
+
+@pytest.mark.parametrize("flag", ["hash", "bits"])
+def test_both_kinds_of_visited_set_are_exact(flag):
+    """A request's visited set is a hash table sized by what the request can see, or a bit per database row
+    (whichever is smaller, unless forced): both must reproduce the oracle's trajectories on integer data.  Two
+    workloads: many short requests through few slots (tables cleared and reused), and requests that walk the whole
+    of a small graph, which fills the small table in front and spills into the large one behind it."""
+    tri, tg = _lib()
+    flags = tg.TRI_GRAPH_VISITED_HASH if flag == "hash" else tg.TRI_GRAPH_VISITED_BITS
+    n, nq, dim, D, M, p, iters = 20_000, 200, 96, 16, 48, 3, 40
+    Xt, Z = graph_inputs.make_points(n, dim, 8, np.float16, graph_inputs.SEED_POINTS, integer=True)
+    Qt, _ = graph_inputs.make_points(nq, dim, 8, np.float16, graph_inputs.SEED_QUERIES, integer=True)
+    Gt = graph_inputs.make_graph(Z, D, 4, graph_inputs.SEED_EDGES)
+    X, Q, G = Xt.numpy(), Qt.numpy(), Gt.numpy().astype(np.uint32)
+    seeds = graph_inputs.entry_points(n, 24)
+    k = np.random.default_rng(2).integers(1, M + 1, size=nq).astype(np.uint32)
+    metric = (np.arange(nq) % 2).astype(np.uint32)
+    want = _oracle_all(X, G, seeds, Q, k, metric, M, p, iters)
+    for slots, groups in ((32, 2), (5, 3)):
+        with tg.GraphPool(X, G, seeds, tri.TRI_F16, slots=slots, topm=M, parents=p, max_iters=iters, max_outstanding=1024,
+                          groups=groups, flags=flags) as pool:
+            ids, dist, n_out, it, ev, steps = pool.run_all(Q, k, metric)
+            _check_exact((ids, dist, n_out, it, ev), want, k)
+    # whole-graph walks: a ring with chords, every node reachable, topM as long as the limit allows, no early stop
+    # before everything has been seen (integer coordinates on a circle-like curve keep topM changing)
+    rng = np.random.default_rng(5)
+    n2, D2, M2, p2 = 250, 8, 250, 8
+    X2 = rng.integers(-6, 7, size=(n2, 12)).astype(np.float32)
+    G2 = np.stack([(np.arange(n2) + d) % n2 for d in (1, 2, 3, 5, 8, 13, 21, 34)], axis=1).astype(np.uint32)
+    Q2 = rng.integers(-6, 7, size=(40, 12)).astype(np.float32)
+    seeds2 = np.array([0, 125], dtype=np.uint32)
+    k2 = np.full(40, 20, dtype=np.uint32)
+    m2 = (np.arange(40) % 2).astype(np.uint32)
+    want2 = _oracle_all(X2, G2, seeds2, Q2, k2, m2, M2, p2, 1000)
+    _say(f"visited {flag}: whole-graph walks score {np.mean([w['evals'] for w in want2]):.0f} of {n2} rows on average")
+    assert np.mean([w["evals"] for w in want2]) > 0.8 * n2
+    with tg.GraphPool(X2, G2, seeds2, tri.TRI_F32, slots=6, topm=M2, parents=p2, max_iters=1000, max_outstanding=64, groups=2,
+                      flags=flags) as pool:
+        for _ in range(2):                                # twice: the second round runs in tables the first one used
+            ids, dist, n_out, it, ev, steps = pool.run_all(Q2, k2, m2)
+            _check_exact((ids, dist, n_out, it, ev), want2, k2)
 
 
 def test_real_valued_data_same_trajectories_where_no_decision_is_a_near_tie():
