@@ -362,12 +362,88 @@ def batch_config(number, args, tri, workloads, torch, headline):
     return result
 
 
+def rowclass_bench(args, tri, torch):
+    """Side measurement: the list-scan stage for every kind of scan kernel -- row lengths of 512, 1024, 1536 and
+    2048 bytes in fp16 and fp32 (register-resident kernels where they exist, the LDS kernel elsewhere) and two
+    lengths only the LDS kernel's generic path serves.  2M unit-norm vectors each, nlist 2048, 2048 queries per
+    step, nprobe 32, k 10, inner product: every list is probed by about 32 queries, i.e. one full tile."""
+    t_start = time.time()
+    n, nlist, Q, nprobe, k = 2_000_000, 2048, 2048, 32, 10
+    rows = []
+    for tdtype, dim in (("f16", 256), ("f16", 512), ("f16", 768), ("f16", 1024), ("f32", 128), ("f32", 256), ("f32", 384),
+                        ("f32", 512), ("f16", 320), ("f32", 200)):
+        g = torch.Generator(device="cuda").manual_seed(5000 + dim)
+        centres = torch.nn.functional.normalize(torch.randn(nlist, dim, generator=g, device="cuda"), dim=1)
+        tt = torch.float16 if tdtype == "f16" else torch.float32
+        base = torch.empty(n, dim, dtype=tt, device="cuda")
+        for s0 in range(0, n, 1 << 18):
+            m = min(1 << 18, n - s0)
+            c = torch.randint(0, nlist, (m,), generator=g, device="cuda")
+            base[s0:s0 + m] = torch.nn.functional.normalize(centres[c] + 0.05 * torch.randn(m, dim, generator=g, device="cuda"), dim=1).to(tt)
+        c = torch.randint(0, nlist, (Q,), generator=g, device="cuda")
+        queries = torch.nn.functional.normalize(centres[c] + 0.05 * torch.randn(Q, dim, generator=g, device="cuda"), dim=1).to(tt).contiguous()
+        dtype = tri.TRI_F16 if tdtype == "f16" else tri.TRI_F32
+        es = 2 if tdtype == "f16" else 4
+        pool = tri.Pool(slots=Q, items_per_step=Q * nprobe, lists_per_query_step=0, kmax=16, nprobe_max=nprobe, max_indexes=1,
+                        max_total_lists=nlist, max_nlist=nlist, max_dim=dim, max_outstanding=Q * 8, coarse_rows=Q,
+                        flags=tri.TRI_FLAG_PROFILE_SCAN, score_capacity=Q * 16384, own_stream=True)
+        index = pool.build_index(base, dim, nlist, dtype, tri.TRI_IP, 4, centroids=centres.float().cpu().numpy())
+        kk = np.full(Q, k, dtype=np.uint32)
+        pp = np.full(Q, nprobe, dtype=np.uint32)
+        mm = np.full(Q, tri.TRI_IP, dtype=np.uint32)
+
+        def one():
+            t, rc = tri.search_submit_batch_dev(pool.handle, index, queries.data_ptr(), dim * es, Q, kk, pp, mm)
+            assert rc == tri.TRI_OK
+            st = tri.search_step(pool.handle)
+            assert st.retired == Q
+            tri.search_sync(pool.handle)
+            tri.search_poll_batch(pool.handle, t, k)
+
+        t0 = time.perf_counter()
+        while time.perf_counter() - t0 < 0.3:
+            one()
+        tri.tri_pool_kernel_times(pool.handle, reset=True)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            one()
+        torch.cuda.synchronize()
+        ms = (time.perf_counter() - t0) * 1e3 / args.steps
+        kt = tri.tri_pool_kernel_times(pool.handle)
+        nl = max(kt.scan_launches, 1)
+        row_bytes = -(-dim * es // 128) * 128
+        kind = ("register-resident, one wavefront per tile" if (row_bytes in (512, 1024) or (tdtype == "f16" and row_bytes in (1536, 2048)))
+                else "LDS kernel, pipelined" if row_bytes in (1536, 2048) else "LDS kernel, generic")
+        r = {"dtype": tdtype, "dim": dim, "row_bytes": row_bytes, "kernel": kind, "ms_per_step_synchronous": round(ms, 4),
+             "sample_ms": round(kt.sample_ms / nl, 4), "threshold_ms": round(kt.threshold_ms / nl, 4), "main_ms": round(kt.scan_ms / nl, 4),
+             "lists_GB": round(kt.scan_list_bytes / nl / 1e9, 3),
+             "main_launch_GBs": round(kt.scan_unique_bytes / max(kt.scan_ms, 1e-9) / 1e6, 1),
+             "scan_stage_GBs": round(kt.scan_list_bytes / max(kt.sample_ms + kt.threshold_ms + kt.scan_ms, 1e-9) / 1e6, 1),
+             "rescans": tri.tri_pool_candidate_rescans(pool.handle)}
+        log(str(r))
+        rows.append(r)
+        pool.close()
+        del base, queries, pool
+        torch.cuda.empty_cache()
+    best = max(rows, key=lambda r: r["scan_stage_GBs"])
+    print(json.dumps({
+        "metric": "queries/sec at recall@k>=0.9 (1 GPU) + list-scan HBM GB/s as % of peak", "value": None, "unit": "queries/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": 0, "ms_per_step": None, "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "f16/f32", "data": "synthetic",
+        "config": {"workload": f"side measurement: the scan stage per row-length class, {n} unit-norm vectors, nlist {nlist}, {Q} queries/step, "
+                               f"nprobe {nprobe}, k {k}, inner product"},
+        "roofline": {"bound": "hbm", "achieved": best["scan_stage_GBs"], "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": round(best["scan_stage_GBs"] / HBM_PEAK_GBS, 4), "traffic": None, "kernel": "best class: " + best["kernel"]},
+        "row_classes": rows, "cpu_baseline": None, "wall_s_total": round(time.time() - t_start, 1)}), flush=True)
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=100)
     ap.add_argument("--warmup", type=int, default=10)
-    ap.add_argument("--workload", default="config4", choices=["config4", "config2", "config1", "config0", "config3", "graph", "graph-stream"])
+    ap.add_argument("--workload", default="config4", choices=["config4", "config2", "config1", "config0", "config3", "graph", "graph-stream", "rowclasses"])
     ap.add_argument("--only-headline", action="store_true",
                     help="config4: skip the shorter measurements of configurations 0-3 that the default run nests under \"configs\"")
     ap.add_argument("--graph-n", type=int, default=1_000_000, help="graph workload: database rows")
@@ -409,6 +485,8 @@ def main():
         return graph_bench(args, tri, torch)
     if args.workload == "graph-stream":
         return graph_stream_bench(args, tri, torch)
+    if args.workload == "rowclasses":
+        return rowclass_bench(args, tri, torch)
     number = int(args.workload[-1])
     if number == 3:
         print(json.dumps(stream_bench(args, tri, workloads, torch, brief=False)), flush=True)

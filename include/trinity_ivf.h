@@ -99,7 +99,10 @@ int tri_pool_workspace_bytes(const tri_pool_cfg *cfg /*[host]*/, size_t *dev_byt
 
 /* Create a pool on the current HIP device.  All memory is the caller's:
  *  dev_ws [device]: at least dev_bytes as reported above, 256-byte aligned; owned by the pool until
- *      tri_pool_destroy (the caller frees it afterwards).
+ *      tri_pool_destroy (the caller frees it afterwards).  The pool clears part of it here, on its own
+ *      stream, and from then on keeps state in it: no work still pending on another stream may write into it
+ *      (memory recycled by a stream-ordered allocator of another stream can be: take it on the pool's stream,
+ *      or synchronise that stream first).  The same holds for dev_mem and tmp_dev of ivf_build.
  *  pinned_ws [host, page-locked and mapped for the device: hipHostMalloc, a torch tensor with
  *      pin_memory=True] of at least pinned_host_bytes, 256-byte aligned; owned by the pool until
  *      tri_pool_destroy; TRI_EINVAL if the device cannot address it.  NULL: the pool allocates that much

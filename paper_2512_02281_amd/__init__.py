@@ -513,12 +513,20 @@ class Pool:
             self._pinned = torch.empty(pinned_bytes + 256, dtype=torch.uint8, pin_memory=True)
             self.handle = tri_pool_create_static(self.cfg, _aligned(self._pinned), pinned_bytes)
             return
-        self._ws = torch.empty(nbytes + 256, dtype=torch.uint8, device="cuda")
+        self._ws = self._device_bytes(nbytes)
         if self.library_memory:
             self.handle = tri_pool_create(self.cfg, _aligned(self._ws), nbytes)
         else:
             self._pinned = torch.empty(pinned_bytes + 256, dtype=torch.uint8, pin_memory=True)
             self.handle = tri_pool_create(self.cfg, _aligned(self._ws), nbytes, _aligned(self._pinned), pinned_bytes)
+
+    def _device_bytes(self, nbytes: int):
+        """Device memory the pool's stream will work in, allocated as that stream's: torch's allocator hands a
+        freed block to a new tensor of the same stream without waiting, so memory taken on another stream could
+        still be written by that stream's pending kernels (a temporary of theirs) after the library has cleared it."""
+        import torch
+        with torch.cuda.stream(self._stream):
+            return torch.empty(nbytes + 256, dtype=torch.uint8, device="cuda")
 
     def build_index(self, base, dim: int, nlist: int, dtype: int, build_metric: int, train_iters: int,
                     centroids: Optional[np.ndarray] = None, seed: int = 0) -> int:
@@ -527,7 +535,7 @@ class Pool:
         params = ivf_params(dim, nlist, dtype, build_metric, train_iters, seed)
         n = int(base.shape[0])
         nbytes = ivf_build_bytes(params, n)
-        mem = torch.empty(nbytes + 256, dtype=torch.uint8, device="cuda")
+        mem = self._device_bytes(nbytes)
         if isinstance(base, np.ndarray):
             base = np.ascontiguousarray(base)
             base_ptr, on_host = base.ctypes.data, True
@@ -539,7 +547,7 @@ class Pool:
             index = ivf_build(self.handle, params, base_ptr, n, centroids, _aligned(mem), nbytes)
         else:
             tmp_bytes = ivf_build_tmp_bytes(params, n, on_host)
-            tmp = torch.empty(tmp_bytes + 256, dtype=torch.uint8, device="cuda")
+            tmp = self._device_bytes(tmp_bytes)
             index = ivf_build(self.handle, params, base_ptr, n, centroids, _aligned(mem), nbytes, _aligned(tmp), tmp_bytes)
             del tmp
         self._index_mem[index] = mem

@@ -28,7 +28,7 @@
 //    only decides how much is written (about k / sample size of the scores).
 //
 // Two kernels:
-//  * scan_wave_kernel (rows of 512 / 1024 / 1536 bytes): ONE WAVEFRONT PER TILE, no barriers.  The wavefront keeps the tile's 32 query rows in registers as MFMA operands (one
+//  * scan_wave_kernel (rows of 512 / 1024 bytes, fp16 rows of 1536 / 2048 bytes): ONE WAVEFRONT PER TILE, no barriers.  The wavefront keeps the tile's 32 query rows in registers as MFMA operands (one
 //    wavefront per SIMD, so it owns all 512 vector registers) and streams the list through a
 //    register ring of RG 128-byte groups: while group g is multiplied, the 16-byte loads of the
 //    group RG steps ahead are in flight (16-24 KiB per wavefront, never drained at block or -- apart
@@ -576,13 +576,14 @@ static ScanVariant scan_variant(uint32_t klass)
     case 0: return {scan_lds_kernel<TRI_DT_F32, 0, FILTER>, false};
     case 1: return {scan_wave_kernel<TRI_DT_F32, 4, 4, FILTER>, true};
     case 2: return {scan_wave_kernel<TRI_DT_F32, 8, 4, FILTER>, true};
-    case 3: return {scan_lds_kernel<TRI_DT_F32, 12, FILTER>, false};   // (the register-resident form would spill)
+    case 3: return {scan_lds_kernel<TRI_DT_F32, 12, FILTER>, false};   // (the register-resident form spills for fp32 rows this
+                                                                        //  wide, whatever the ring length: 150-350 bytes per lane)
     case 4: return {scan_lds_kernel<TRI_DT_F32, 16, FILTER>, false};
     case 5: return {scan_lds_kernel<TRI_DT_F16, 0, FILTER>, false};
     case 6: return {scan_wave_kernel<TRI_DT_F16, 4, 4, FILTER>, true};
     case 7: return {scan_wave_kernel<TRI_DT_F16, 8, 4, FILTER>, true};
     case 8: return {scan_wave_kernel<TRI_DT_F16, 12, 6, FILTER>, true};
-    default: return {scan_lds_kernel<TRI_DT_F16, 16, FILTER>, false};
+    default: return {scan_wave_kernel<TRI_DT_F16, 16, 4, FILTER>, true};   // (2048-byte fp16 rows: 256 query registers + a 4-group ring still fit)
     }
 }
 

@@ -83,7 +83,8 @@ class GraphPool:
                                  self._stream.cuda_stream)
         nbytes = ctypes.c_size_t(0)
         _check(_lib.graph_pool_bytes(ctypes.byref(self.cfg), n, dim, degree, dtype, ctypes.byref(nbytes)), "graph_pool_bytes")
-        self._mem = torch.empty(nbytes.value + 256, dtype=torch.uint8, device="cuda")
+        with torch.cuda.stream(self._stream):       # the pool's stream works in it: allocated as that stream's memory
+            self._mem = torch.empty(nbytes.value + 256, dtype=torch.uint8, device="cuda")
         ptr = (self._mem.data_ptr() + 255) // 256 * 256
         vectors = np.ascontiguousarray(vectors) if isinstance(vectors, np.ndarray) else vectors.contiguous()
         neighbors = np.ascontiguousarray(neighbors, dtype=np.uint32) if isinstance(neighbors, np.ndarray) else neighbors.contiguous()

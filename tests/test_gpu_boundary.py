@@ -164,3 +164,28 @@ def test_a_step_that_fails_half_way_marks_the_pool_failed():
             assert ei.value.status == tri.TRI_EHIP and "failed earlier" in str(ei.value) and "injected" in str(ei.value)
     # (leaving the block destroyed the index and the pool without an error)
     assert pool.handle is None
+
+
+def test_a_pool_on_its_own_stream_is_not_written_by_work_pending_on_another():
+    """The binding takes a pool's device memory as memory of the pool's stream.  Taken on torch's current stream
+    instead, a block that a temporary of still-pending kernels had just given back could be handed out, cleared by
+    the library on the pool's stream and then written by those kernels: state that starts at zero (the count of
+    candidate-region rescans is such a word) would hold their data."""
+    import torch
+    tri = harness.lib()
+    cfg, base_t, queries_t, base, queries, rows = _small_f16(tri, n_queries=64)
+    for _ in range(3):
+        x = torch.randn(1 << 24, device="cuda")
+        for _ in range(8):
+            x = x * 1.0001 + 0.04          # every line frees a 64 MiB temporary while its kernel is still queued
+        del x
+        with harness.default_pool(tri, slots=64, lists_per_query_step=8, max_dim=cfg.dim, max_nlist=64, max_total_lists=64,
+                                  own_stream=True) as pool:
+            torch.cuda.synchronize()
+            assert tri.tri_pool_candidate_rescans(pool.handle) == 0
+            idx = pool.build_index(base_t, cfg.dim, cfg.nlist, tri.TRI_F16, tri.TRI_IP, 2, centroids=base[rows].astype(np.float32))
+            ids, dist, n_out, probes, _ = _search_all(tri, pool, idx, queries, 10, 8)
+            oidx = harness.oracle_index(tri, idx, base)
+            rep = harness.compare_with_oracle(oidx, base, queries, 10, 8, 1, ids, dist, n_out, probes)
+            assert rep["checked"] == cfg.n_queries
+            assert tri.tri_pool_candidate_rescans(pool.handle) == 0
