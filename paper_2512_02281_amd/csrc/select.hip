@@ -794,7 +794,206 @@ hipError_t tri_launch_coarse_select(const TriLaunchCtx &c, const TriDevWs &ws, u
 // sample scores (the first TRI_SAMPLE_VECS vectors of up to TRI_THRESH_ITEMS of its lists) and its
 // running top-k -- a subset of its candidates, so nothing of its final top-k lies beyond it.  Fewer
 // than k such keys: no filtering (all-ones).
-__global__ __launch_bounds__(TRI_SEL_THREADS) void slot_threshold_kernel(
+//
+// ONE WAVEFRONT PER SLOT, four slots per workgroup, no workgroup barriers: the keys sit in registers (lane l
+// holds sample l of every item, and every 64th entry of the running top-k), the histogram of the bucket cut is
+// the wavefront's own 8 KB of LDS, and whatever the lanes have to agree on goes through cross-lane operations.
+// A wavefront's LDS operations execute in program order, so its histogram needs no more than compiler fences.
+#define THR_TOPK_PER 4        // entries of the running top-k per lane in registers (256); a longer one: the slow cut
+
+__device__ __forceinline__ void thr_wave_fence()
+{
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
+
+// Inclusive scan of one value per lane across the wavefront with data-parallel-primitive moves instead of trips
+// through the LDS crossbar: four shifts inside each row of 16 lanes (a lane that has no source keeps `ident`), then
+// lane 15 of rows 0 and 2 is broadcast into rows 1 and 3, then lane 31 into rows 2 and 3.  op(a, ident) == a.
+__device__ __forceinline__ uint32_t thr_bits(uint32_t x) { return x; }
+__device__ __forceinline__ uint32_t thr_bits(float x) { return __float_as_uint(x); }
+__device__ __forceinline__ void thr_unbits(uint32_t b, uint32_t &x) { x = b; }
+__device__ __forceinline__ void thr_unbits(uint32_t b, float &x) { x = __uint_as_float(b); }
+
+template <int CTRL, int ROW_MASK, class T>
+__device__ __forceinline__ T thr_dpp(T v, T ident)
+{
+    T r;
+    thr_unbits((uint32_t)__builtin_amdgcn_update_dpp((int)thr_bits(ident), (int)thr_bits(v), CTRL, ROW_MASK, 0xF, false), r);
+    return r;
+}
+
+template <class T, class Op>
+__device__ __forceinline__ T thr_wave_scan(T v, T ident, Op op)
+{
+    v = op(v, thr_dpp<0x111, 0xF>(v, ident));      // row_shr:1
+    v = op(v, thr_dpp<0x112, 0xF>(v, ident));      // row_shr:2
+    v = op(v, thr_dpp<0x114, 0xF>(v, ident));      // row_shr:4
+    v = op(v, thr_dpp<0x118, 0xF>(v, ident));      // row_shr:8
+    v = op(v, thr_dpp<0x142, 0xA>(v, ident));      // row_bcast:15 into rows 1 and 3
+    v = op(v, thr_dpp<0x143, 0xC>(v, ident));      // row_bcast:31 into rows 2 and 3
+    return v;
+}
+
+template <class T, class Op>
+__device__ __forceinline__ T thr_wave_reduce(T v, T ident, Op op)
+{
+    T r;
+    thr_unbits((uint32_t)__builtin_amdgcn_readlane((int)thr_bits(thr_wave_scan(v, ident, op)), 63), r);
+    return r;
+}
+
+template <uint32_t BINS = SEL_BINS>
+__device__ __forceinline__ void thr_hist_zero(uint32_t *hist, uint32_t lane)
+{
+#pragma unroll
+    for (uint32_t i = 0; i < BINS / 256; ++i) ((uint4 *)hist)[i * 64 + lane] = make_uint4(0u, 0u, 0u, 0u);
+    thr_wave_fence();
+}
+
+// Smallest bucket B of the wavefront's histogram whose cumulative count reaches need (256 bins a round, four
+// consecutive ones per lane, a prefix sum across the lanes).  in_bucket = hist[B], need_in = need - (count below B).
+template <uint32_t BINS = SEL_BINS>
+__device__ __forceinline__ void thr_hist_find(const uint32_t *hist, uint32_t need, uint32_t lane, uint32_t &B,
+                                              uint32_t &in_bucket, uint32_t &need_in)
+{
+    thr_wave_fence();
+    B = BINS - 1;
+    in_bucket = 0;
+    need_in = need;
+    uint32_t run = 0;
+    for (uint32_t j = 0; j < BINS / 256; ++j) {
+        const uint4 h = ((const uint4 *)hist)[j * 64 + lane];
+        const uint32_t mine = h.x + h.y + h.z + h.w;
+        const uint32_t incl = thr_wave_scan(mine, 0u, [](uint32_t a, uint32_t b) { return a + b; });
+        const uint32_t excl = run + incl - mine;
+        const bool here = excl < need && need <= excl + mine;
+        const uint64_t who = __ballot(here);
+        if (who) {
+            uint32_t b = 0, cnt = 0, left = 0;
+            if (here) {
+                const uint32_t hh[4] = {h.x, h.y, h.z, h.w};
+                uint32_t r2 = excl;
+                bool found = false;
+#pragma unroll
+                for (int c = 0; c < 4; ++c) {
+                    if (!found && r2 + hh[c] >= need) {
+                        b = j * 256 + lane * 4 + c;
+                        cnt = hh[c];
+                        left = need - r2;
+                        found = true;
+                    }
+                    r2 += hh[c];
+                }
+            }
+            const int src = __ffsll((unsigned long long)who) - 1;
+            B = (uint32_t)__builtin_amdgcn_readlane((int)b, src);
+            in_bucket = (uint32_t)__builtin_amdgcn_readlane((int)cnt, src);
+            need_in = (uint32_t)__builtin_amdgcn_readlane((int)left, src);
+            return;
+        }
+        run += (uint32_t)__builtin_amdgcn_readlane((int)incl, 63);
+    }
+}
+
+// The values a wavefront selects from: val = the score where smaller is better, its negative where larger is
+// (so smaller is always better); +infinity = absent.  tri_score_key(val, 0) is the key of the score.
+struct ThrVals {
+    float item[TRI_THRESH_ITEMS];     // lane l: sample l of item s
+    float topk[THR_TOPK_PER];         // lane l: entry 64 s + l of the running top-k
+};
+
+template <class Fn>
+__device__ __forceinline__ void thr_for_each(const ThrVals &v, Fn f)
+{
+#pragma unroll
+    for (int s = 0; s < TRI_THRESH_ITEMS; ++s) f(v.item[s]);
+#pragma unroll
+    for (int s = 0; s < THR_TOPK_PER; ++s) f(v.topk[s]);
+}
+
+// Exact-to-the-key cut, for the cases the one-pass cut below does not settle: a key T with at least m of the
+// wavefront's keys not above it and few more.  Buckets linear in the key, the bucket of rank m cut again (each level
+// narrows the key range 2048-fold) until it holds at most a few keys beyond rank m or equal keys only.  Rare;
+// for_each_key(f) reads the keys again from memory (all-ones for absent ones), f(key) called by all lanes together,
+// so that it needs none of the registers of the common path.
+template <class ForEachKey>
+__device__ __forceinline__ uint32_t thr_wave_refine(ForEachKey for_each_key, uint32_t m, uint32_t *hist, uint32_t lane)
+{
+    uint32_t range_lo = 0u, range_hi = 0xFFFFFFFEu;
+    uint32_t need = m, t = 0xFFFFFFFEu;
+    for (int level = 0; level < 4; ++level) {
+        uint32_t lo = 0xFFFFFFFFu, hi = 0u;
+        for_each_key([&](uint32_t k) {
+            if (k >= range_lo && k <= range_hi) {
+                lo = k < lo ? k : lo;
+                hi = k > hi ? k : hi;
+            }
+        });
+        const uint32_t kmin = thr_wave_reduce(lo, 0xFFFFFFFFu, [](uint32_t a, uint32_t b) { return a < b ? a : b; });
+        const uint32_t kmax = thr_wave_reduce(hi, 0u, [](uint32_t a, uint32_t b) { return a > b ? a : b; });
+        const float scale = kmax > kmin ? ((float)SEL_BINS - 0.01f) / (float)(kmax - kmin) : 0.f;
+        thr_hist_zero(hist, lane);
+        for_each_key([&](uint32_t k) {
+            if (k >= range_lo && k <= range_hi) atomicAdd(&hist[sel_bucket(k, kmin, scale)], 1u);
+        });
+        uint32_t B, in_bucket, need_in;
+        thr_hist_find(hist, need, lane, B, in_bucket, need_in);
+        uint32_t best = 0u, least = 0xFFFFFFFFu;
+        for_each_key([&](uint32_t k) {
+            if (k >= range_lo && k <= range_hi && sel_bucket(k, kmin, scale) == B) {
+                best = k > best ? k : best;
+                least = k < least ? k : least;
+            }
+        });
+        t = thr_wave_reduce(best, 0u, [](uint32_t a, uint32_t b) { return a > b ? a : b; });
+        const uint32_t t_lo = thr_wave_reduce(least, 0xFFFFFFFFu, [](uint32_t a, uint32_t b) { return a < b ? a : b; });
+        if (in_bucket <= need_in + 4u || t_lo == t) break;
+        range_lo = t_lo;
+        range_hi = t;
+        need = need_in;
+    }
+    return t;
+}
+
+// A value E with at least m of the wavefront's values not above it, and few more (at least m values are present;
+// for_each(f) calls f(x) for every value the wavefront holds in registers, +infinity = absent).
+// One pass: buckets linear in the VALUE between the smallest and the largest one (keys are bit patterns of floats:
+// linear in the key, the best scores of a set that straddles zero crowd into a handful of buckets), E = the upper
+// edge of the bucket that holds rank m.  The edge is computed in floating point, so the count of values not above
+// it is checked; false for a crowded bucket (more than `slack` values beyond rank m) or a failed check.
+template <uint32_t BINS = SEL_BINS, class ForEach>
+__device__ __forceinline__ bool sel_wave_cut(ForEach for_each, uint32_t m, uint32_t slack, uint32_t *hist, uint32_t lane,
+                                             float &edge)
+{
+    float lo = INFINITY, hi = -INFINITY;
+    for_each([&](float x) {
+        if (x < INFINITY) {
+            lo = fminf(lo, x);
+            hi = fmaxf(hi, x);
+        }
+    });
+    lo = thr_wave_reduce(lo, INFINITY, [](float a, float b) { return fminf(a, b); });
+    hi = thr_wave_reduce(hi, -INFINITY, [](float a, float b) { return fmaxf(a, b); });
+    const float span = hi - lo;
+    if (!(span > 0.f && span < 3.0e38f)) return false;
+    const float scale = ((float)BINS - 0.01f) / span;
+    thr_hist_zero<BINS>(hist, lane);
+    for_each([&](float x) {
+        if (x < INFINITY) atomicAdd(&hist[(uint32_t)fminf((x - lo) * scale, (float)(BINS - 1))], 1u);
+    });
+    uint32_t B, in_bucket, need_in;
+    thr_hist_find<BINS>(hist, m, lane, B, in_bucket, need_in);
+    if (in_bucket > need_in + slack) return false;
+    edge = B >= BINS - 1 ? hi : fminf(lo + (float)(B + 1) / scale, hi);
+    uint32_t c = 0;
+    for_each([&](float x) { c += x <= edge; });
+    c = thr_wave_reduce(c, 0u, [](uint32_t a, uint32_t b) { return a + b; });
+    return c >= m;
+}
+
+__global__ __launch_bounds__(TRI_SEL_THREADS) __attribute__((amdgpu_waves_per_eu(4, 4))) void slot_threshold_kernel(
     const uint8_t *__restrict__ upload, const TriSlotMeta *__restrict__ slot_meta,
     const uint32_t *__restrict__ item_glist, const uint32_t *__restrict__ item_sorted_pos,
     const uint32_t *__restrict__ glist_len, const uint32_t *__restrict__ glist_voff,
@@ -802,95 +1001,125 @@ __global__ __launch_bounds__(TRI_SEL_THREADS) void slot_threshold_kernel(
     const uint32_t *__restrict__ topk_count, uint32_t kmax, uint32_t *__restrict__ thr_key, uint2 *__restrict__ cand,
     uint32_t *__restrict__ slot_cand_off, uint32_t *__restrict__ slot_cand_cap, uint32_t *__restrict__ slot_cand_cnt)
 {
-    static_assert(TRI_SAMPLE_VECS % TRI_VB == 0 && TRI_VB == 32, "the sample is the first blocks of a list");
-    static_assert(TRI_THRESH_ITEMS * TRI_SAMPLE_VECS + TRI_KMAX_POW2 <= 2 * SEL_CAP, "the sample keys must fit the LDS array");
-    __shared__ SelShared sh;
+    static_assert(TRI_SAMPLE_VECS == 64 && TRI_THRESH_ITEMS == 64, "lane l holds sample l of item s in register s");
+    __shared__ __attribute__((aligned(16))) uint32_t hist_all[TRI_SEL_THREADS / 64][SEL_BINS];
+    __shared__ uint32_t item_all[TRI_SEL_THREADS / 64][3][TRI_THRESH_ITEMS];
+    const uint32_t lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    uint32_t *hist = hist_all[wave], *voffs = item_all[wave][0], *rows = item_all[wave][1], *lens = item_all[wave][2];
     const TriStepHdr *hdr = (const TriStepHdr *)upload;
-    if (blockIdx.x >= hdr->n_plan) return;
-    const TriPlanEntry e = ((const TriPlanEntry *)(upload + hdr->plan_off))[blockIdx.x];
+    const uint32_t pe = blockIdx.x * (TRI_SEL_THREADS / 64) + wave;
+    if (pe >= hdr->n_plan) return;                           // (per wavefront; the kernel has no workgroup barrier)
+    const TriPlanEntry e = ((const TriPlanEntry *)(upload + hdr->plan_off))[pe];
     const TriSlotMeta meta = slot_meta[e.slot];
-    const uint32_t desc = meta.metric == 1u;
-    const uint32_t have = e.cursor > 0 ? topk_count[e.slot] : 0u;
+    const bool desc = meta.metric == 1u;
+    const uint32_t have = e.cursor > 0 ? min(topk_count[e.slot], (uint32_t)TRI_KMAX_POW2) : 0u;
     const uint32_t nitems = e.take < TRI_THRESH_ITEMS ? e.take : TRI_THRESH_ITEMS;
-    uint32_t *keys = (uint32_t *)sh.pool;                  // room for 2 * SEL_CAP keys
-    // per item (kept in the segment cache, which this kernel does not use otherwise): .off = its sample
-    // row, .len = how many of its TRI_SAMPLE_VECS scores exist, .id_off = stored position of its list's first vector
-    const uint32_t ncached = e.take < SEL_SEGCACHE ? e.take : SEL_SEGCACHE;
-    if (threadIdx.x == 0) sh.cnt = 0;
-    for (uint32_t s = threadIdx.x; s < ncached; s += TRI_SEL_THREADS) {
-        const uint32_t it = e.item_base + s, g = item_glist[it];
-        sh.seg[s] = SelSeg{item_sorted_pos[it], min(glist_len[g], (uint32_t)TRI_SAMPLE_VECS), glist_voff[g], 0u};
+    // lane s: sample row and sample count of item s; first stored position of its list -> LDS
+    uint32_t it_row = 0, it_len = 0;
+    if (lane < nitems) {
+        const uint32_t it = e.item_base + lane, g = item_glist[it];
+        it_row = item_sorted_pos[it];
+        it_len = min(glist_len[g], (uint32_t)TRI_SAMPLE_VECS);
+        voffs[lane] = glist_voff[g];
+        rows[lane] = it_row;
+        lens[lane] = it_len;
     }
-    __syncthreads();
-    // keys[s * TRI_SAMPLE_VECS + l] = key of sample l of item s (all-ones where the list is shorter), then the running top-k
-    const uint32_t nsample = nitems * TRI_SAMPLE_VECS, n = nsample + have;
-    uint32_t valid_here = 0;
-    for (uint32_t i = threadIdx.x; i < n; i += TRI_SEL_THREADS) {
-        uint32_t key = 0xFFFFFFFFu;
-        if (i < nsample) {
-            const uint32_t s = i / TRI_SAMPLE_VECS, l = i % TRI_SAMPLE_VECS;
-            if (l < sh.seg[s].len) key = sel_key(sample_scores[(size_t)sh.seg[s].off * TRI_SAMPLE_VECS + l], desc);
-        } else {
-            key = sel_key(topk_score[(size_t)e.slot * kmax + (i - nsample)], desc);
-        }
-        keys[i] = key;
-        valid_here += key != 0xFFFFFFFFu;
-    }
-    if (valid_here) atomicAdd(&sh.cnt, valid_here);
-    __syncthreads();
-    const uint32_t nvalid = sh.cnt;
-    __syncthreads();
-    uint32_t thr = 0xFFFFFFFFu;
-    if (nvalid >= meta.k) thr = sel_keys_threshold(sh, keys, n, meta.k);
-    if (threadIdx.x == 0) {
-        thr_key[e.slot] = thr;
-        sh.count = 0;                     // (the selection above used it; from here on: pairs emitted)
-    }
-    __syncthreads();
-    // The sample IS the first block(s) of every list: its scores that pass the threshold become the first
-    // candidates of the query's region here, and the scan starts every list behind them.  One item per
-    // half-wavefront; (score bits, stored position) pairs, placed through one LDS counter; the main launch counts
-    // on from what this leaves in the slot's counter.
-    // (The first TRI_THRESH_ITEMS items' keys are still in LDS -- a key gives back its score bit for bit --;
-    // items beyond them, and beyond the cached descriptors, are read again.)
-    const uint32_t l32 = threadIdx.x & 31;
-    for (uint32_t s = threadIdx.x >> 5; s < e.take; s += TRI_SEL_THREADS / 32) {
-        uint32_t row, n_l, voff;
-        if (s < ncached) {
-            row = sh.seg[s].off; n_l = sh.seg[s].len; voff = sh.seg[s].id_off;
-        } else {
-            const uint32_t it = e.item_base + s, g = item_glist[it];
-            row = item_sorted_pos[it];
-            n_l = min(glist_len[g], (uint32_t)TRI_SAMPLE_VECS);
-            voff = glist_voff[g];
-        }
+    // All loads first (every address valid: absent items read item 0's row, and a row always has TRI_SAMPLE_VECS
+    // entries); what is absent -- a list shorter than the sample, fewer items, a shorter running top-k -- then
+    // becomes +infinity.  Row starts travel as scalar offsets of a buffer load, so no address is kept per item.
+    const __amdgpu_buffer_rsrc_t srs = __builtin_amdgcn_make_buffer_rsrc((void *)sample_scores, 0, 0xFFFFFFFFu, 0x00020000);
+    const float pad = desc ? -INFINITY : INFINITY;           // (before the sign is settled)
+    ThrVals v;
 #pragma unroll
-        for (uint32_t sb = 0; sb < TRI_SAMPLE_VECS / 32; ++sb) {      // 32 samples at a time
-            const uint32_t l = sb * 32 + l32;
-            uint32_t key = 0xFFFFFFFFu;
-            if (l < n_l) key = s < nitems ? keys[s * TRI_SAMPLE_VECS + l] : sel_key(sample_scores[(size_t)row * TRI_SAMPLE_VECS + l], desc);
-            const bool pass = l < n_l && key <= thr;
-            const uint64_t m = __ballot(pass);
-            const uint32_t half = (threadIdx.x & 32) ? (uint32_t)(m >> 32) : (uint32_t)m;
-            uint32_t first = 0;
-            if (l32 == 0 && half) first = atomicAdd(&sh.count, (uint32_t)__popc(half));
-            first = (uint32_t)__shfl((int)first, (int)(threadIdx.x & 32), 64);
-            const uint32_t pos = first + __popc(half & ((1u << l32) - 1u));
-            if (pass && pos < e.cand_cap) cand[(size_t)e.cand_off + pos] = make_uint2(__float_as_uint(sel_unkey(key, desc)), voff + l);
+    for (int s = 0; s < TRI_THRESH_ITEMS; ++s) {
+        const uint32_t row = __builtin_amdgcn_readlane(it_row, s);
+        v.item[s] = __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(srs, lane * 4u, row * (TRI_SAMPLE_VECS * 4u), 0));
+    }
+#pragma unroll
+    for (int s = 0; s < THR_TOPK_PER; ++s) {
+        const uint32_t i = s * 64 + lane;
+        v.topk[s] = i < have ? topk_score[(size_t)e.slot * kmax + i] : pad;
+    }
+    uint64_t there = 0;                                      // bit s: this lane's sample of item s exists
+#pragma unroll
+    for (int s = 0; s < TRI_THRESH_ITEMS; ++s)
+        there |= (uint64_t)(lane < __builtin_amdgcn_readlane(it_len, s) ? 1u : 0u) << s;
+    uint32_t present = 0;
+#pragma unroll
+    for (int s = 0; s < TRI_THRESH_ITEMS; ++s) v.item[s] = (there >> s) & 1u ? (desc ? -v.item[s] : v.item[s]) : INFINITY;
+#pragma unroll
+    for (int s = 0; s < THR_TOPK_PER; ++s) v.topk[s] = desc ? -v.topk[s] : v.topk[s];
+#pragma unroll
+    for (int s = 0; s < TRI_THRESH_ITEMS; ++s) present += v.item[s] < INFINITY;
+    present = thr_wave_reduce(present, 0u, [](uint32_t a, uint32_t b) { return a + b; }) + have;
+    uint32_t thr = 0xFFFFFFFFu;
+    // (beyond rank k the cut may admit a few keys, or an eighth of k: that many more candidates pass the scan's filter)
+    float cut = 0.f;
+    const bool enough = present >= meta.k;
+    const bool settled = enough && have <= 64u * THR_TOPK_PER &&
+                         sel_wave_cut([&](auto f) { thr_for_each(v, f); }, meta.k, max(8u, meta.k >> 3), hist, lane, cut);
+    // The sample IS the first block(s) of every list: its scores that pass the threshold become the first
+    // candidates of the query's region here, and the scan starts every list behind them.  (score bits, stored
+    // position) pairs; the main launch counts on from what this leaves in the slot's counter.
+    uint32_t count = 0;
+    auto emit = [&](bool pass, float val, uint32_t pos0) {
+        const uint64_t m = __ballot(pass);
+        const uint32_t pos = count + __builtin_amdgcn_mbcnt_hi((uint32_t)(m >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)m, 0u));
+        const float score = desc ? -val : val;
+        if (pass && pos < e.cand_cap)
+            cand[(size_t)e.cand_off + pos] = make_uint2(score == 0.f ? 0u : __float_as_uint(score), pos0 + lane);
+        count += (uint32_t)__popcll(m);
+    };
+    thr_wave_fence();                                        // (voffs, rows, lens)
+    uint32_t from_memory = 0;                                // first item whose samples are read again below
+    if (settled) {
+        thr = tri_score_key(cut, 0u);
+        const float edge = tri_key_score(thr, 0u);           // (value <= edge: its key is not above thr)
+#pragma unroll
+        for (int s = 0; s < TRI_THRESH_ITEMS; ++s)
+            if (__ballot(v.item[s] <= edge)) emit(v.item[s] <= edge, v.item[s], voffs[s]);    // (uniform; most rows pass nothing)
+        from_memory = TRI_THRESH_ITEMS;
+    } else if (enough) {
+        thr = thr_wave_refine([&](auto f) {
+            for (uint32_t s = 0; s < nitems; ++s) {
+                float x = lane < lens[s] ? sample_scores[(size_t)rows[s] * TRI_SAMPLE_VECS + lane] : pad;
+                x = desc ? -x : x;
+                f(x < INFINITY ? tri_score_key(x, 0u) : 0xFFFFFFFFu);
+            }
+            for (uint32_t i0 = 0; i0 < have; i0 += 64) {
+                float x = i0 + lane < have ? topk_score[(size_t)e.slot * kmax + i0 + lane] : pad;
+                x = desc ? -x : x;
+                f(x < INFINITY ? tri_score_key(x, 0u) : 0xFFFFFFFFu);
+            }
+        }, meta.k, hist, lane);
+    }
+    // From memory: items beyond those the threshold was made of; every item where the one-pass cut did not settle the
+    // threshold (the registers of the common path are not kept for that), or where there is none (the value that
+    // stands for "absent" cannot tell an absent sample from a score of infinity, the lists' lengths can).
+    {
+        const bool all = thr == 0xFFFFFFFFu;
+        const float edge = tri_key_score(thr, 0u);
+        for (uint32_t s = from_memory; s < e.take; ++s) {
+            const uint32_t it = e.item_base + s, g = item_glist[it];
+            const uint32_t len = min(glist_len[g], (uint32_t)TRI_SAMPLE_VECS), voff = glist_voff[g];
+            float val = lane < len ? sample_scores[(size_t)item_sorted_pos[it] * TRI_SAMPLE_VECS + lane] : pad;
+            if (desc) val = -val;
+            emit(lane < len && (all || val <= edge), val, voff);
         }
     }
-    __syncthreads();
-    if (threadIdx.x == 0) {
+    if (lane == 0) {
+        thr_key[e.slot] = thr;
         slot_cand_off[e.slot] = e.cand_off;
         slot_cand_cap[e.slot] = e.cand_cap;
-        slot_cand_cnt[e.slot] = sh.count;
+        slot_cand_cnt[e.slot] = count;
     }
 }
 
 hipError_t tri_launch_threshold(const TriLaunchCtx &c, const TriDevWs &ws, uint32_t grid_plan)
 {
     if (grid_plan == 0) return hipSuccess;
-    hipLaunchKernelGGL(slot_threshold_kernel, dim3(grid_plan), dim3(TRI_SEL_THREADS), 0, c.stream, ws.upload, ws.slot_meta,
+    hipLaunchKernelGGL(slot_threshold_kernel, dim3((grid_plan + TRI_SEL_THREADS / 64 - 1) / (TRI_SEL_THREADS / 64)),
+                       dim3(TRI_SEL_THREADS), 0, c.stream, ws.upload, ws.slot_meta,
                        ws.item_glist, ws.item_sorted_pos, ws.glist_len, ws.glist_voff, ws.sample_scores, ws.topk_score,
                        ws.topk_count, c.kmax, ws.thr_key, ws.cand, ws.slot_cand_off, ws.slot_cand_cap, ws.slot_cand_cnt);
     return hipGetLastError();
@@ -920,47 +1149,274 @@ __device__ __forceinline__ float sel_l2_diff_form(const uint8_t *__restrict__ x,
 }
 
 // ------------------------------------------------------------------------------------------------
-// Slot merge: one workgroup per running slot of the step.  Candidates = the (score, stored position) pairs
-// the scan kept in the slot's region of the candidate buffer in this step + its running top-k.  Should the
-// region have been too small (the slot's counter ran past its capacity), the pairs in it are ignored and the
-// slot's lists of this step are scored again right here (SelRescan): slow, exact, and rare.
-// Output = new running top-k, or -- when the slot retires in this step -- its final result.
-__global__ __launch_bounds__(TRI_SEL_THREADS) void slot_merge_kernel(
-    const uint8_t *__restrict__ upload, const TriSlotMeta *__restrict__ slot_meta,
-    const TriIndexDev *__restrict__ indexes, const uint32_t *__restrict__ item_glist,
-    const uint32_t *__restrict__ slot_cand_cnt, const uint32_t *__restrict__ glist_len,
-    const uint32_t *__restrict__ glist_voff, const uint2 *__restrict__ cand, float *__restrict__ topk_score,
-    uint32_t *__restrict__ topk_id, uint32_t *__restrict__ topk_count, uint32_t kmax,
-    uint32_t *__restrict__ res_block, const uint32_t *__restrict__ probe, uint32_t nprobe_max,
-    uint32_t *__restrict__ res_probes, const uint8_t *__restrict__ slot_query, uint32_t slot_row_bytes,
-    const float *__restrict__ slot_qnorm, uint32_t *__restrict__ rescans)
+// Slot merge.  Candidates of a running slot = the (score, stored position) pairs the scan kept in the slot's
+// region of the candidate buffer in this step + its running top-k.  Output = the new running top-k, or -- when
+// the slot retires in this step -- its final result.
+//
+// Two kernels.  In the first every slot is tried by one wavefront on its own (merge_wave: candidates in
+// registers, one-pass cut, survivors sorted by rank counting in the wavefront's LDS; no workgroup barrier).  Slots
+// that do not settle there -- too many candidates or survivors, masses of equal scores, a candidate region that
+// was too small -- are queued and taken by the second, one workgroup per slot with the general selection
+// (merge_block).  Should a region have been too small (the slot's counter ran past its capacity), the pairs in it are
+// ignored and the slot's lists of this step are scored again right here (SelRescan): slow, exact, and rare.
+struct MergeArgs {
+    const uint8_t *upload;
+    const TriSlotMeta *slot_meta;
+    const TriIndexDev *indexes;
+    const uint32_t *item_glist, *slot_cand_cnt, *glist_len, *glist_voff;
+    const uint2 *cand;
+    float *topk_score;
+    uint32_t *topk_id, *topk_count;
+    uint32_t kmax;
+    uint32_t *res_block;
+    const uint32_t *probe;
+    uint32_t nprobe_max;
+    uint32_t *res_probes;
+    const uint8_t *slot_query;
+    uint32_t slot_row_bytes;
+    const float *slot_qnorm;
+    uint32_t *rescans;               // [0] counter of rescans, [1], [2] entries in merge_queue (one head per parity of the launch)
+    uint32_t *merge_queue;
+};
+
+#define MRG_PER 24           // candidates per lane the wavefront path holds in registers (1536 per slot)
+#define MRG_BINS 1024
+#define MRG_TOPK_PER 4       // entries of the running top-k per lane (256)
+#define MRG_CAP 256          // survivors it sorts
+
+struct MergeWaveLds {
+    uint32_t hist[MRG_BINS];
+    uint64_t a[MRG_CAP], b[MRG_CAP];
+};
+
+// Sort c <= MRG_CAP composites by rank counting within one wavefront, src -> dst (LDS, distinct): a lane owns the
+// elements lane, lane + 64, ... and counts, for each, the elements ordered before it (every lane reads the same
+// element at a time, a broadcast; four reads are in flight together).
+__device__ __forceinline__ void mrg_rank_sort(const uint64_t *src, uint32_t c, uint64_t *dst, uint32_t lane)
 {
-    __shared__ SelShared sh;
-    const TriStepHdr *hdr = (const TriStepHdr *)upload;
-    if (blockIdx.x >= hdr->n_plan) return;
-    const TriPlanEntry e = ((const TriPlanEntry *)(upload + hdr->plan_off))[blockIdx.x];
-    const TriSlotMeta meta = slot_meta[e.slot];
+    thr_wave_fence();
+    constexpr int OWN = MRG_CAP / 64;
+    uint64_t x[OWN];
+    uint32_t rank[OWN];
+#pragma unroll
+    for (int j = 0; j < OWN; ++j) {
+        x[j] = j * 64 + lane < c ? src[j * 64 + lane] : ~0ull;
+        rank[j] = 0;
+    }
+    const uint32_t own = (c + 63) / 64;                                 // (uniform)
+    auto count = [&](uint64_t y, uint32_t u) {
+#pragma unroll
+        for (int j = 0; j < OWN; ++j)
+            if ((uint32_t)j < own) rank[j] += (y < x[j] || (y == x[j] && u < j * 64 + lane)) ? 1u : 0u;
+    };
+    uint32_t u = 0;
+    for (; u + 4 <= c; u += 4) {
+        const uint64_t y0 = src[u], y1 = src[u + 1], y2 = src[u + 2], y3 = src[u + 3];
+        count(y0, u);
+        count(y1, u + 1);
+        count(y2, u + 2);
+        count(y3, u + 3);
+    }
+    for (; u < c; ++u) count(src[u], u);
+    thr_wave_fence();
+#pragma unroll
+    for (int j = 0; j < OWN; ++j)
+        if (j * 64 + lane < c) dst[rank[j]] = x[j];
+    thr_wave_fence();
+}
+
+// Results of a slot: to the record of a retiring query (pinned host memory), else to its running top-k.
+// best[0..n): sorted composites (LDS); called by `nthreads` threads with index `tid`.
+__device__ __forceinline__ void mrg_write_out(const MergeArgs &A, const TriPlanEntry &e, const TriSlotMeta &meta, uint32_t desc,
+                                              const uint64_t *best, uint32_t n, uint32_t tid, uint32_t nthreads)
+{
+    if (e.retire_idx >= 0) {
+        uint32_t *rec = A.res_block + (size_t)e.retire_idx * (1u + 2u * A.kmax);
+        if (tid == 0) rec[0] = n;
+        for (uint32_t i = tid; i < n; i += nthreads) {
+            const uint64_t c = best[i];
+            rec[1 + i] = (uint32_t)(c & 0xFFFFFFFFu);
+            rec[1 + A.kmax + i] = __float_as_uint(sel_unkey((uint32_t)(c >> 32), desc));
+        }
+        if (A.res_probes) {
+            const uint32_t *srcp = A.probe + (size_t)e.slot * A.nprobe_max;
+            uint32_t *dst = A.res_probes + (size_t)e.retire_idx * A.nprobe_max;
+            for (uint32_t i = tid; i < meta.nprobe; i += nthreads) dst[i] = srcp[i];
+        }
+    } else {
+        float *run_score = A.topk_score + (size_t)e.slot * A.kmax;
+        uint32_t *run_id = A.topk_id + (size_t)e.slot * A.kmax;
+        for (uint32_t i = tid; i < n; i += nthreads) {
+            const uint64_t c = best[i];
+            run_id[i] = (uint32_t)(c & 0xFFFFFFFFu);
+            run_score[i] = sel_unkey((uint32_t)(c >> 32), desc);
+        }
+        if (tid == 0) A.topk_count[e.slot] = n;
+    }
+}
+
+// The k best of a slot's candidates, by one wavefront: for_each(f) calls f(value, payload, is_pair) for every
+// candidate (value: smaller is better, +infinity = absent; payload: stored position of a pair, id of a running
+// entry; all pairs before the running entries), all lanes together.  Leaves the c survivors of the cut in L.a as
+// (key, id) composites -- those of the pairs first, from_pairs of them, with the stored position in the id's place.
+// false: not settled.
+template <class ForEach>
+__device__ __forceinline__ bool mrg_wave_select(ForEach for_each, uint32_t total, uint32_t k, bool desc, MergeWaveLds &L,
+                                                uint32_t lane, uint32_t &c, uint32_t &from_pairs)
+{
+    uint32_t present = 0;
+    for_each([&](float x, uint32_t, bool) { present += x < INFINITY; });
+    present = thr_wave_reduce(present, 0u, [](uint32_t a, uint32_t b) { return a + b; });
+    if (present != total) return false;                                       // (scores that are infinite or not numbers)
+    float edge = INFINITY;
+    if (total > k &&
+        !sel_wave_cut<MRG_BINS>([&](auto f) { for_each([&](float x, uint32_t, bool) { f(x); }); }, k, MRG_CAP - k, L.hist, lane, edge))
+        return false;
+    uint32_t cnt = 0, pairs = 0;
+    for_each([&](float x, uint32_t payload, bool is_pair) {
+        const bool pass = x <= edge && x < INFINITY;
+        const uint64_t m = __ballot(pass);
+        if (m == 0) return;                                                 // (uniform)
+        const uint32_t at = cnt + __builtin_amdgcn_mbcnt_hi((uint32_t)(m >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)m, 0u));
+        if (pass && at < MRG_CAP) L.a[at] = ((uint64_t)sel_key(desc ? -x : x, desc) << 32) | payload;
+        cnt += (uint32_t)__popcll(m);
+        if (is_pair) pairs = cnt;
+    });
+    c = cnt;
+    from_pairs = pairs;
+    return c <= MRG_CAP;
+}
+
+// One slot by one wavefront.  false: not settled, nothing written.
+__device__ __forceinline__ bool merge_wave(const MergeArgs &A, const TriPlanEntry &e, MergeWaveLds &L, uint32_t lane)
+{
+    const TriSlotMeta meta = A.slot_meta[e.slot];
+    const bool desc = meta.metric == 1u;
+    const uint32_t k = meta.k;
+    const uint32_t asked = A.slot_cand_cnt[e.slot];
+    const uint32_t have = e.cursor > 0 ? A.topk_count[e.slot] : 0u;
+    if (asked > e.cand_cap || k > MRG_CAP) return false;
+    const TriIndexDev &ix = A.indexes[meta.index];
+    const float *run_score = A.topk_score + (size_t)e.slot * A.kmax;
+    const uint32_t *run_id = A.topk_id + (size_t)e.slot * A.kmax;
+    const uint2 *mine = A.cand + e.cand_off;
+    uint32_t c = 0, from_pairs = 0;
+    bool settled;
+    if (asked <= 64u * MRG_PER && have <= 64u * MRG_TOPK_PER) {
+        // the usual size: everything in registers, read once (all loads are issued before the first value is
+        // looked at: one round trip to memory, not one per 64 pairs)
+        float val[MRG_PER], rv[MRG_TOPK_PER];
+        uint32_t pos[MRG_PER], rid[MRG_TOPK_PER];
+        uint2 raw[MRG_PER];
+#pragma unroll
+        for (int j = 0; j < MRG_PER; ++j) {
+            raw[j] = make_uint2(0u, 0u);
+            if ((uint32_t)j * 64 < asked) raw[j] = mine[j * 64 + lane < asked ? j * 64 + lane : 0u];    // (uniform)
+        }
+#pragma unroll
+        for (int j = 0; j < MRG_TOPK_PER; ++j) {
+            const uint32_t i = j * 64 + lane;
+            rv[j] = i < have ? run_score[i] : 0.f;
+            rid[j] = i < have ? run_id[i] : 0u;
+        }
+#pragma unroll
+        for (int j = 0; j < MRG_PER; ++j) {
+            const float sc = __uint_as_float(raw[j].x);
+            val[j] = (uint32_t)j * 64 + lane < asked ? (desc ? -sc : sc) : INFINITY;
+            pos[j] = raw[j].y;
+        }
+#pragma unroll
+        for (int j = 0; j < MRG_TOPK_PER; ++j) rv[j] = (uint32_t)j * 64 + lane < have ? (desc ? -rv[j] : rv[j]) : INFINITY;
+        settled = mrg_wave_select([&](auto f) {
+#pragma unroll
+            for (int j = 0; j < MRG_PER; ++j) f(val[j], pos[j], true);
+#pragma unroll
+            for (int j = 0; j < MRG_TOPK_PER; ++j) f(rv[j], rid[j], false);
+        }, asked + have, k, desc, L, lane, c, from_pairs);
+    } else {
+        // more than the registers hold: every pass reads the candidates again, eight loads per lane in flight
+        settled = mrg_wave_select([&](auto f) {
+            constexpr int U = 8;
+            for (uint32_t i0 = 0; i0 < asked; i0 += 64 * U) {
+                uint2 raw[U];
+#pragma unroll
+                for (int u = 0; u < U; ++u) raw[u] = mine[i0 + u * 64 + lane < asked ? i0 + u * 64 + lane : 0u];
+#pragma unroll
+                for (int u = 0; u < U; ++u) {
+                    const float sc = __uint_as_float(raw[u].x);
+                    f(i0 + u * 64 + lane < asked ? (desc ? -sc : sc) : INFINITY, raw[u].y, true);
+                }
+            }
+            for (uint32_t i0 = 0; i0 < have; i0 += 64) {
+                const float sc = i0 + lane < have ? run_score[i0 + lane] : 0.f;
+                f(i0 + lane < have ? (desc ? -sc : sc) : INFINITY, i0 + lane < have ? run_id[i0 + lane] : 0u, false);
+            }
+        }, asked + have, k, desc, L, lane, c, from_pairs);
+    }
+    if (!settled) return false;
+    // the ids of the survivors that came from pairs are fetched together (one round trip to memory for all of them)
+    thr_wave_fence();
+    {
+        uint64_t x[MRG_CAP / 64];
+#pragma unroll
+        for (int j = 0; j < MRG_CAP / 64; ++j) x[j] = j * 64 + lane < from_pairs ? L.a[j * 64 + lane] : 0ull;
+        uint32_t id[MRG_CAP / 64];
+#pragma unroll
+        for (int j = 0; j < MRG_CAP / 64; ++j) id[j] = j * 64 + lane < from_pairs ? ix.ids[(uint32_t)(x[j] & 0xFFFFFFFFu)] : 0u;
+#pragma unroll
+        for (int j = 0; j < MRG_CAP / 64; ++j)
+            if (j * 64 + lane < from_pairs) L.a[j * 64 + lane] = (x[j] & 0xFFFFFFFF00000000ull) | id[j];
+    }
+    mrg_rank_sort(L.a, c, L.b, lane);
+    uint32_t n = c < k ? c : k;
+    const uint64_t *best = L.b;
+    if (e.retire_idx >= 0 && !desc && n > 0) {
+        // squared L2 handed back in the difference form (see merge_block): the n survivors are scored again, one row
+        // per half-wavefront at a time, and put in the order of those scores
+        const uint8_t *qrow = A.slot_query + (size_t)e.slot * A.slot_row_bytes;
+        const uint32_t l32 = lane & 31;
+        uint32_t *stored = L.hist;                                              // (where each survivor's row is: fetched together; n <= MRG_CAP <= MRG_BINS)
+        for (uint32_t i = lane; i < n; i += 64) stored[i] = ix.inv[(uint32_t)(L.b[i] & 0xFFFFFFFFu)];
+        thr_wave_fence();
+        for (uint32_t i = lane >> 5; i < n; i += 2) {
+            const uint32_t id = (uint32_t)(L.b[i] & 0xFFFFFFFFu);
+            const uint8_t *x = (const uint8_t *)ix.vecs + (size_t)stored[i] * ix.row_bytes;
+            const float d2 = ix.dtype == 1u ? sel_l2_diff_form<_Float16>(x, qrow, ix.row_bytes, l32)
+                                            : sel_l2_diff_form<float>(x, qrow, ix.row_bytes, l32);
+            if (l32 == 0) L.a[i] = ((uint64_t)sel_key(d2, 0u) << 32) | id;
+        }
+        mrg_rank_sort(L.a, n, L.b, lane);
+    }
+    mrg_write_out(A, e, meta, desc ? 1u : 0u, best, n, lane, 64u);
+    return true;
+}
+
+// One slot by the whole workgroup, any size.
+__device__ void merge_block(const MergeArgs &A, const TriPlanEntry &e, SelShared &sh)
+{
+    const TriSlotMeta meta = A.slot_meta[e.slot];
     const uint32_t desc = meta.metric == 1u;
-    const uint32_t have = e.cursor > 0 ? topk_count[e.slot] : 0u;
-    float *run_score = topk_score + (size_t)e.slot * kmax;
-    uint32_t *run_id = topk_id + (size_t)e.slot * kmax;
-    const uint32_t asked = slot_cand_cnt[e.slot];
+    const uint32_t have = e.cursor > 0 ? A.topk_count[e.slot] : 0u;
+    float *run_score = A.topk_score + (size_t)e.slot * A.kmax;
+    uint32_t *run_id = A.topk_id + (size_t)e.slot * A.kmax;
+    const uint32_t asked = A.slot_cand_cnt[e.slot];
     const bool overflow = asked > e.cand_cap;                 // (the same for every thread of the workgroup)
-    SelRescan rs = {item_glist, glist_len, glist_voff, &indexes[meta.index], slot_query + (size_t)e.slot * slot_row_bytes,
-                    slot_qnorm[e.slot], meta.metric == 0u, e.item_base, e.take, 0u};
+    SelRescan rs = {A.item_glist, A.glist_len, A.glist_voff, &A.indexes[meta.index],
+                    A.slot_query + (size_t)e.slot * A.slot_row_bytes, A.slot_qnorm[e.slot], meta.metric == 0u, e.item_base,
+                    e.take, 0u};
     if (overflow) {
         uint32_t part = 0;
-        for (uint32_t it = threadIdx.x; it < e.take; it += TRI_SEL_THREADS) part += glist_len[item_glist[e.item_base + it]];
+        for (uint32_t it = threadIdx.x; it < e.take; it += TRI_SEL_THREADS) part += A.glist_len[A.item_glist[e.item_base + it]];
         const uint32_t incl = sel_block_scan_incl(part, sh.wave_tot);
         if (threadIdx.x == TRI_SEL_THREADS - 1) {
             sh.tmax = incl;
-            atomicAdd(rescans, 1u);
+            atomicAdd(A.rescans, 1u);
         }
         __syncthreads();
         rs.total = sh.tmax;
         __syncthreads();
     }
-    const SelSrc src = {cand, indexes[meta.index].ids, run_score, run_id, overflow ? 0u : 1u, have, overflow ? &rs : nullptr};
+    const SelSrc src = {A.cand, A.indexes[meta.index].ids, run_score, run_id, overflow ? 0u : 1u, have, overflow ? &rs : nullptr};
     auto seg_of = [&](uint32_t) { return SelSeg{e.cand_off, asked, 0u, 0u}; };
     uint32_t n;
     const uint64_t *best = sel_block_topk<true>(sh, src, seg_of, meta.k, desc, &n);
@@ -971,8 +1427,8 @@ __global__ __launch_bounds__(TRI_SEL_THREADS) void slot_merge_kernel(
         // handed back when a query nearly coincides with a stored vector.  The k survivors of a retiring
         // query are scored again in the difference form (k rows re-read: nothing beside the scan) and put in
         // the order of those scores (equal scores by ascending id, as everywhere).
-        const TriIndexDev &ix = indexes[meta.index];
-        const uint8_t *qrow = slot_query + (size_t)e.slot * slot_row_bytes;
+        const TriIndexDev &ix = A.indexes[meta.index];
+        const uint8_t *qrow = A.slot_query + (size_t)e.slot * A.slot_row_bytes;
         uint64_t *fresh = best == sh.pool ? sh.small : sh.pool;             // (n <= kmax <= SEL_SMALL)
         const uint32_t l32 = threadIdx.x & 31;
         for (uint32_t i = threadIdx.x >> 5; i < n; i += TRI_SEL_THREADS / 32) {
@@ -989,36 +1445,46 @@ __global__ __launch_bounds__(TRI_SEL_THREADS) void slot_merge_kernel(
         }
         best = sel_pool_topk(sh, n, n);
     }
-    if (e.retire_idx >= 0) {
-        uint32_t *rec = res_block + (size_t)e.retire_idx * (1u + 2u * kmax);
-        if (threadIdx.x == 0) rec[0] = n;
-        for (uint32_t i = threadIdx.x; i < n; i += TRI_SEL_THREADS) {
-            const uint64_t c = best[i];
-            rec[1 + i] = (uint32_t)(c & 0xFFFFFFFFu);
-            rec[1 + kmax + i] = __float_as_uint(sel_unkey((uint32_t)(c >> 32), desc));
-        }
-        if (res_probes) {
-            const uint32_t *srcp = probe + (size_t)e.slot * nprobe_max;
-            uint32_t *dst = res_probes + (size_t)e.retire_idx * nprobe_max;
-            for (uint32_t i = threadIdx.x; i < meta.nprobe; i += TRI_SEL_THREADS) dst[i] = srcp[i];
-        }
-    } else {
-        for (uint32_t i = threadIdx.x; i < n; i += TRI_SEL_THREADS) {
-            const uint64_t c = best[i];
-            run_id[i] = (uint32_t)(c & 0xFFFFFFFFu);
-            run_score[i] = sel_unkey((uint32_t)(c >> 32), desc);
-        }
-        if (threadIdx.x == 0) topk_count[e.slot] = n;
-    }
+    mrg_write_out(A, e, meta, desc, best, n, threadIdx.x, TRI_SEL_THREADS);
+    __syncthreads();                                          // (the workgroup's next slot reuses sh)
+}
+
+__global__ __launch_bounds__(TRI_SEL_THREADS) __attribute__((amdgpu_waves_per_eu(4, 4))) void slot_merge_wave_kernel(const MergeArgs A)
+{
+    constexpr uint32_t NW = TRI_SEL_THREADS / 64;
+    __shared__ MergeWaveLds wv[NW];
+    const uint32_t lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const TriStepHdr *hdr = (const TriStepHdr *)A.upload;
+    const uint32_t pe = blockIdx.x * NW + wave;
+    if (pe >= hdr->n_plan) return;                           // (per wavefront; the kernel has no workgroup barrier)
+    const TriPlanEntry *plan = (const TriPlanEntry *)(A.upload + hdr->plan_off);
+    if (!merge_wave(A, plan[pe], wv[wave], lane) && lane == 0) A.merge_queue[atomicAdd(A.rescans + 1 + hdr->merge_parity, 1u)] = pe;
+}
+
+// The slots the kernel above left, dealt out among a fixed number of workgroups.  There are two queue heads, used in
+// turn by successive launches: this launch reads its own and clears the other one, for the next launch.
+__global__ __launch_bounds__(TRI_SEL_THREADS) void slot_merge_block_kernel(const MergeArgs A)
+{
+    __shared__ SelShared sh;
+    const TriStepHdr *hdr = (const TriStepHdr *)A.upload;
+    const TriPlanEntry *plan = (const TriPlanEntry *)(A.upload + hdr->plan_off);
+    if (hdr->n_plan == 0) return;                            // (a replayed launch of a step without a plan: not a turn)
+    const uint32_t parity = hdr->merge_parity & 1u;
+    if (blockIdx.x == 0 && threadIdx.x == 0) A.rescans[1 + (parity ^ 1u)] = 0;
+    const uint32_t queued = A.rescans[1 + parity];
+    for (uint32_t i = blockIdx.x; i < queued; i += gridDim.x) merge_block(A, plan[A.merge_queue[i]], sh);   // (uniform)
 }
 
 hipError_t tri_launch_merge(const TriLaunchCtx &c, const TriDevWs &ws, uint32_t grid_plan, bool keep_probes)
 {
     if (grid_plan == 0) return hipSuccess;
-    hipLaunchKernelGGL(slot_merge_kernel, dim3(grid_plan), dim3(TRI_SEL_THREADS), 0, c.stream, ws.upload, ws.slot_meta,
-                       ws.indexes, ws.item_glist, ws.slot_cand_cnt, ws.glist_len, ws.glist_voff, ws.cand, ws.topk_score,
-                       ws.topk_id, ws.topk_count, c.kmax, ws.res_block, ws.probe, c.nprobe_max,
-                       keep_probes ? ws.res_probes : (uint32_t *)nullptr, ws.slot_query, c.slot_row_bytes, ws.slot_qnorm,
-                       ws.rescans);
+    const MergeArgs A = {ws.upload, ws.slot_meta, ws.indexes, ws.item_glist, ws.slot_cand_cnt, ws.glist_len, ws.glist_voff, ws.cand,
+                         ws.topk_score, ws.topk_id, ws.topk_count, c.kmax, ws.res_block, ws.probe, c.nprobe_max,
+                         keep_probes ? ws.res_probes : (uint32_t *)nullptr, ws.slot_query, c.slot_row_bytes, ws.slot_qnorm,
+                         ws.rescans, ws.merge_queue};
+    constexpr uint32_t NW = TRI_SEL_THREADS / 64;
+    hipLaunchKernelGGL(slot_merge_wave_kernel, dim3((grid_plan + NW - 1) / NW), dim3(TRI_SEL_THREADS), 0, c.stream, A);
+    const uint32_t general = grid_plan < c.n_cu * 4 ? grid_plan : c.n_cu * 4;
+    hipLaunchKernelGGL(slot_merge_block_kernel, dim3(general), dim3(TRI_SEL_THREADS), 0, c.stream, A);
     return hipGetLastError();
 }

@@ -163,6 +163,7 @@ struct tri_pool {
     std::vector<uint32_t> free_slots;
     uint32_t n_running = 0;
     uint64_t admit_seq = 0, step_seq = 0;
+    uint32_t merge_launches = 0;      // parity of the merge kernels' queue heads
     StepRec ring[RING];
     uint8_t *pinned = nullptr;         // upload / result blocks of the steps in flight, then the query store
     bool own_pinned = false;           // allocated here (hipHostMalloc) and freed in tri_pool_destroy
@@ -247,6 +248,7 @@ size_t carve(const tri_pool_cfg &c, uint32_t max_row_bytes, uint32_t coarse_rows
     CARVE(slot_cand_cap, uint32_t *, S * 4)
     CARVE(slot_cand_cnt, uint32_t *, S * 4)
     CARVE(rescans, uint32_t *, 256)
+    CARVE(merge_queue, uint32_t *, S * 4)
     CARVE(step_dev, TriStepDev *, 256)
     CARVE(cand, uint2 *, (size_t)score_capacity * 4)
     // (res_block / res_probes point into the pinned host block of the step in flight: set per step)
@@ -561,7 +563,7 @@ extern "C" int tri_pool_create(const tri_pool_cfg *cfg, void *dev_ws, size_t dev
         if (e != hipSuccess) { delete P; return tri_fail(TRI_EHIP, "hipHostMalloc(%zu) -> %s", L.total, hipGetErrorString(e)); }
         P->own_pinned = true;
     }
-    e = tri_launch_fill_u32(P->stream, P->ws.rescans, 0u, 1);
+    e = tri_launch_fill_u32(P->stream, P->ws.rescans, 0u, 4);
     if (e == hipSuccess) e = hipStreamSynchronize(P->stream);
     if (e != hipSuccess) { tri_pool_destroy(P); return tri_fail(TRI_EHIP, "workspace set-up -> %s", hipGetErrorString(e)); }
     P->qstore = P->pinned + L.qstore_off;
@@ -1426,6 +1428,7 @@ int step_locked(tri_pool *P, tri_step_stats *st)
         a = b;
     }
     hdr_h->n_groups = n_groups;
+    hdr_h->merge_parity = n_plan ? (P->merge_launches++ & 1u) : 0u;   // (the merge kernels run when the step has a plan)
 
     if (P->inject_failure) {
         P->inject_failure = false;

@@ -73,7 +73,8 @@ struct TriStepHdr {
     uint32_t plan_off;
     uint32_t rows_off;       // row area (filled on the device by the admit kernel)
     uint32_t n_groups;
-    uint32_t pad_[7];
+    uint32_t merge_parity;   // which of the two queue heads of the merge kernels this step uses (alternates with every merge launch)
+    uint32_t pad_[6];
     TriCoarseGroup group[TRI_MAX_COARSE_GROUPS];
 };
 static_assert(sizeof(TriStepHdr) == 1024, "header is 1024 bytes");
@@ -100,7 +101,7 @@ struct TriTile {
 };
 
 #define TRI_SAMPLE_VECS 64     // vectors per list scored ahead of the scan to find each query's threshold
-#define TRI_THRESH_ITEMS 72    // at most this many items' samples enter one query's threshold
+#define TRI_THRESH_ITEMS 64    // at most this many items' samples enter one query's threshold (one register per item)
 
 // Order-preserving image of an fp32 score: ascending key = better (bit-flipped for inner product).
 __device__ __forceinline__ uint32_t tri_score_key(float f, uint32_t descending)
@@ -172,7 +173,10 @@ struct TriDevWs {
     uint32_t *slot_cand_off;  // [S] this step's region of the slot in the candidate buffer: first pair,
     uint32_t *slot_cand_cap;  // [S]   pairs it holds,
     uint32_t *slot_cand_cnt;  // [S]   pairs asked for so far (beyond cap: not stored, the merge then re-scans)
-    uint32_t *rescans;        // [1] slots whose region overflowed and whose lists the merge kernel scored again (since creation)
+    uint32_t *rescans;        // [0] slots whose region overflowed and whose lists the merge kernel scored again (since creation);
+                              // [1], [2]: entries in merge_queue, one head for each parity of the merge launches (a launch
+                              // fills and reads its own and clears the other)
+    uint32_t *merge_queue;    // [S] plan entries of the step that the one-wavefront merge did not settle
     TriStepDev *step_dev;     // [1]
     uint2 *cand;              // [score_capacity / 2] candidate buffer: (score bits, stored position) pairs
     // results of retiring slots, compact, per step
