@@ -273,12 +273,11 @@ __global__ __launch_bounds__(1024) void pack_scan_kernel(const uint32_t *__restr
 }
 
 // (3) scatter: one thread per item -> list-sorted slot array.
-__global__ void pack_scatter_kernel(const TriStepHdr *__restrict__ hdr, const uint32_t *__restrict__ item_glist,
-                                    const uint32_t *__restrict__ item_slot, const uint32_t *__restrict__ item_rank,
-                                    const uint32_t *__restrict__ list_start, uint32_t *__restrict__ sorted_slot,
-                                    uint32_t *__restrict__ item_sorted_pos)
+__device__ __forceinline__ void pack_scatter(uint32_t i, const TriStepHdr *__restrict__ hdr, const uint32_t *__restrict__ item_glist,
+                                             const uint32_t *__restrict__ item_slot, const uint32_t *__restrict__ item_rank,
+                                             const uint32_t *__restrict__ list_start, uint32_t *__restrict__ sorted_slot,
+                                             uint32_t *__restrict__ item_sorted_pos)
 {
-    const uint32_t i = blockIdx.x * blockDim.x + threadIdx.x;
     if (i >= hdr->n_items) return;
     const uint32_t g = item_glist[i], r = item_rank[i];
     sorted_slot[list_start[g] + r] = item_slot[i];
@@ -287,20 +286,21 @@ __global__ void pack_scatter_kernel(const TriStepHdr *__restrict__ hdr, const ui
 
 // (4) tiles: one thread per list of the pool-wide table.  A list longer than its chunk length is cut into
 //     chunks; the tiles of one chunk (one per group of TRI_QT queries) are adjacent in the queue.  Every
-//     list also gets its sample tiles (first TRI_SAMPLE_VECS vectors, one per group of queries).
-__global__ void pack_tiles_kernel(uint32_t total_lists, const uint32_t *__restrict__ hist,
-                                  const uint32_t *__restrict__ list_start, const uint32_t *__restrict__ tile_base,
-                                  const uint32_t *__restrict__ stile_base,
-                                  const uint32_t *__restrict__ glist_len, const uint32_t *__restrict__ glist_voff,
-                                  const uint32_t *__restrict__ glist_index, const TriIndexDev *__restrict__ indexes,
-                                  const TriStepHdr *__restrict__ hdr, TriTile *__restrict__ tiles,
-                                  TriTile *__restrict__ stiles)
+//     list also gets its sample tiles (first TRI_SAMPLE_VECS vectors, one per group of queries).  This is the
+//     last reader of the histogram: it puts the list's count back to zero, which is how the next step finds it.
+__device__ __forceinline__ void pack_tiles(uint32_t g, uint32_t total_lists, uint32_t *__restrict__ hist,
+                                           const uint32_t *__restrict__ list_start, const uint32_t *__restrict__ tile_base,
+                                           const uint32_t *__restrict__ stile_base,
+                                           const uint32_t *__restrict__ glist_len, const uint32_t *__restrict__ glist_voff,
+                                           const uint32_t *__restrict__ glist_index, const TriIndexDev *__restrict__ indexes,
+                                           const TriStepHdr *__restrict__ hdr, TriTile *__restrict__ tiles,
+                                           TriTile *__restrict__ stiles)
 {
-    const uint32_t g = blockIdx.x * blockDim.x + threadIdx.x;
     if (g >= total_lists) return;
     const uint32_t min_chunk = hdr->min_chunk;
     const uint32_t c = hist[g];
     const uint32_t len = glist_len[g];
+    if (c) hist[g] = 0;
     if (!c || !len) return;
     const TriIndexDev &ix = indexes[glist_index[g]];
     const uint32_t nt = (c + TRI_QT - 1) / TRI_QT;
@@ -341,13 +341,31 @@ __global__ void pack_tiles_kernel(uint32_t total_lists, const uint32_t *__restri
     }
 }
 
+// (3) + (4) in one launch: the first item_blocks workgroups scatter, the others make tiles (neither reads what
+//     the other writes).
+__global__ void pack_place_kernel(uint32_t item_blocks, uint32_t total_lists, uint32_t *__restrict__ hist,
+                                  const uint32_t *__restrict__ item_glist, const uint32_t *__restrict__ item_slot,
+                                  const uint32_t *__restrict__ item_rank, const uint32_t *__restrict__ list_start,
+                                  uint32_t *__restrict__ sorted_slot, uint32_t *__restrict__ item_sorted_pos,
+                                  const uint32_t *__restrict__ tile_base, const uint32_t *__restrict__ stile_base,
+                                  const uint32_t *__restrict__ glist_len, const uint32_t *__restrict__ glist_voff,
+                                  const uint32_t *__restrict__ glist_index, const TriIndexDev *__restrict__ indexes,
+                                  const TriStepHdr *__restrict__ hdr, TriTile *__restrict__ tiles, TriTile *__restrict__ stiles)
+{
+    if (blockIdx.x < item_blocks)
+        pack_scatter(blockIdx.x * blockDim.x + threadIdx.x, hdr, item_glist, item_slot, item_rank, list_start, sorted_slot,
+                     item_sorted_pos);
+    else
+        pack_tiles((blockIdx.x - item_blocks) * blockDim.x + threadIdx.x, total_lists, hist, list_start, tile_base, stile_base,
+                   glist_len, glist_voff, glist_index, indexes, hdr, tiles, stiles);
+}
+
 hipError_t tri_launch_pack(const TriLaunchCtx &c, const TriDevWs &ws, uint32_t grid_items, uint32_t total_lists,
                            uint32_t n_order)
 {
     if (total_lists == 0) return hipSuccess;
     const TriStepHdr *hdr = (const TriStepHdr *)ws.upload;
-    hipError_t e = tri_launch_fill_u32(c.stream, ws.hist, 0u, total_lists);
-    if (e != hipSuccess) return e;
+    // (the histogram of items per list is all zero here: so the pool starts, and so every step leaves it)
     if (grid_items)
         hipLaunchKernelGGL(pack_emit_kernel, dim3((grid_items + 255) / 256), dim3(256), 0, c.stream, ws.upload,
                            ws.slot_meta, ws.indexes, ws.probe, c.nprobe_max, ws.item_glist, ws.item_slot,
@@ -360,11 +378,10 @@ hipError_t tri_launch_pack(const TriLaunchCtx &c, const TriDevWs &ws, uint32_t g
     hipLaunchKernelGGL(pack_scan_kernel<true>, dim3(nb ? nb : 1), dim3(1024), 0, c.stream, ws.hist, n_order, ws.glist_order,
                        ws.list_start, ws.tile_base, ws.stile_base, ws.step_dev, ws.tile_counter, hdr,
                        ws.pack_tot, ws.step_host);
-    if (grid_items)
-        hipLaunchKernelGGL(pack_scatter_kernel, dim3((grid_items + 255) / 256), dim3(256), 0, c.stream, hdr,
-                           ws.item_glist, ws.item_slot, ws.item_rank, ws.list_start, ws.sorted_slot, ws.item_sorted_pos);
-    hipLaunchKernelGGL(pack_tiles_kernel, dim3((total_lists + 255) / 256), dim3(256), 0, c.stream, total_lists,
-                       ws.hist, ws.list_start, ws.tile_base, ws.stile_base, ws.glist_len, ws.glist_voff,
-                       ws.glist_index, ws.indexes, hdr, ws.tiles, ws.stiles);
+    const uint32_t item_blocks = (grid_items + 255) / 256;
+    hipLaunchKernelGGL(pack_place_kernel, dim3(item_blocks + (total_lists + 255) / 256), dim3(256), 0, c.stream, item_blocks,
+                       total_lists, ws.hist, ws.item_glist, ws.item_slot, ws.item_rank, ws.list_start, ws.sorted_slot,
+                       ws.item_sorted_pos, ws.tile_base, ws.stile_base, ws.glist_len, ws.glist_voff, ws.glist_index,
+                       ws.indexes, hdr, ws.tiles, ws.stiles);
     return hipGetLastError();
 }

@@ -181,10 +181,12 @@ __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(1, 1))) void
     uint32_t t = 0;
     if (lane == 0) t = atomicAdd(tile_counter, 1u);
     t = __builtin_amdgcn_readfirstlane(t);
+    TriTile tl_ahead = tiles[t < n_tiles ? t : 0u];        // (the queue's capacity is never zero)
     while (t < n_tiles) {
-        const TriTile tl = tiles[t];
+        const TriTile tl = tl_ahead;
         uint32_t t_next = 0;                    // claimed now, needed only when this tile is done
         if (lane == 0) t_next = atomicAdd(tile_counter, 1u);
+        bool ahead = false;                     // the next tile's descriptor has been asked for
         if (tl.klass == my_class) {
             const uint32_t len = tl.vec_count;
             const uint32_t nblocks = (len + TRI_VB - 1) / TRI_VB;
@@ -274,6 +276,14 @@ __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(1, 1))) void
                     for (int c = 0; c < 4; ++c) buf[sl][c] = scan_ld16(vrs, nxt + c * 32);
                     __builtin_amdgcn_sched_barrier(0);
                 }
+                if (!ahead) {
+                    // The claim of the next tile has come back by now (it was issued before this tile's first
+                    // loads, and loads return in order): its descriptor is fetched while the rest of this tile
+                    // streams, through the scalar path, which the vector loads' bookkeeping does not see.
+                    const uint32_t tn = __builtin_amdgcn_readfirstlane(t_next);
+                    tl_ahead = tiles[tn < n_tiles ? tn : 0u];
+                    ahead = true;
+                }
                 if constexpr (FILTER) {
                     const uint32_t vpos = b * TRI_VB + r;
                     if (stage_n > SCAN_STAGE_CAP - TRI_QT * TRI_VB)     // (uniform, and rare: a few dozen pass per block)
@@ -290,6 +300,7 @@ __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(1, 1))) void
                                  (uint2 *)out_buf, pos_base);
         }
         t = __builtin_amdgcn_readfirstlane(t_next);
+        if (!ahead) tl_ahead = tiles[t < n_tiles ? t : 0u];   // (a tile of another class, or one without a block to score)
     }
 }
 

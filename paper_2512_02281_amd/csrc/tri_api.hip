@@ -563,7 +563,9 @@ extern "C" int tri_pool_create(const tri_pool_cfg *cfg, void *dev_ws, size_t dev
         if (e != hipSuccess) { delete P; return tri_fail(TRI_EHIP, "hipHostMalloc(%zu) -> %s", L.total, hipGetErrorString(e)); }
         P->own_pinned = true;
     }
+    // what must start at zero: the rescan counter and the merge kernels' queue heads; the items-per-list histogram
     e = tri_launch_fill_u32(P->stream, P->ws.rescans, 0u, 4);
+    if (e == hipSuccess) e = tri_launch_fill_u32(P->stream, P->ws.hist, 0u, cfg->max_total_lists);
     if (e == hipSuccess) e = hipStreamSynchronize(P->stream);
     if (e != hipSuccess) { tri_pool_destroy(P); return tri_fail(TRI_EHIP, "workspace set-up -> %s", hipGetErrorString(e)); }
     P->qstore = P->pinned + L.qstore_off;
