@@ -1054,3 +1054,37 @@ def test_largest_k_and_nprobe():
             true_ids, _ = bruteforce.knn(base, queries[i:i + 1], int(k[i]), int(metric[i]))
             common = len(set(ids[i, :k[i]].tolist()) & set(true_ids[0].tolist()))
             assert common >= int(k[i]) - 1, f"query {i}: nprobe = nlist must be exact kNN ({common} of {k[i]})"
+
+
+@pytest.mark.parametrize("lists_per_step", [0, 2])
+def test_every_path_of_the_per_slot_selection_kernels(lists_per_step):
+    """The threshold and merge kernels take a slot by one wavefront when it fits their registers and their one-pass
+    cut settles it, and otherwise by slower routes.  Built to reach all of them, every result against the oracle:
+    no threshold at all (fewer samples than k: every vector of the probed lists is a candidate, far more than the
+    merge's registers hold, so it streams them pass by pass); running top-k across steps (with lists_per_step 2);
+    k above 256 (the general workgroup selection, and a running top-k longer than the threshold kernel's registers);
+    and samples with extreme outliers -- stored vectors of huge norm with the smallest ids, so that they head every
+    list's sample -- which stretch the value range until the bucket of rank k holds nearly everything and the cut
+    has to be refined."""
+    tri = harness.lib()
+    rng = np.random.default_rng(77)
+    n, d, nlist = 24_000, 64, 12
+    centres = rng.normal(0.0, 1.0, size=(nlist, d))
+    base = (centres[rng.integers(0, nlist, n)] + rng.normal(0.0, 0.5, size=(n, d))).astype(np.float32)
+    base[:nlist * 2] = (centres[np.arange(nlist * 2) % nlist] * 400.0).astype(np.float32)      # outliers, smallest ids
+    cases = [(200, 2, 0), (200, 2, 1), (250, 6, 0), (100, 8, 1), (10, 8, 0), (300, 4, 1), (700, 6, 0), (1, 3, 1), (64, 12, 0)]
+    nq = 6 * len(cases)
+    queries = np.ascontiguousarray((centres[rng.integers(0, nlist, nq)] + rng.normal(0.0, 0.5, size=(nq, d))).astype(np.float32))
+    k = np.array([cases[i % len(cases)][0] for i in range(nq)], dtype=np.uint32)
+    nprobe = np.array([cases[i % len(cases)][1] for i in range(nq)], dtype=np.uint32)
+    metric = np.array([cases[i % len(cases)][2] for i in range(nq)], dtype=np.uint32)
+    with harness.default_pool(tri, slots=32, lists_per_query_step=lists_per_step, kmax=1024, max_dim=d, max_nlist=nlist,
+                              max_total_lists=nlist, score_capacity=1 << 22) as pool:
+        idx = pool.build_index(base, d, nlist, tri.TRI_F32, tri.TRI_L2, 0, centroids=centres.astype(np.float32))
+        oidx = harness.oracle_index(tri, idx, base)
+        q = tri.make_queries(idx, queries, k, nprobe, metric)
+        ids, dist, n_out, probes, stats = harness.run_all(tri, pool, q)
+        rep = harness.compare_with_oracle(oidx, base, queries, k, nprobe, metric, ids, dist, n_out, probes)
+        _say(f"selection paths, {lists_per_step or 'all'} lists per step: {len(stats)} steps, parity {rep}, "
+             f"rescans {tri.tri_pool_candidate_rescans(pool.handle)}")
+        assert rep["checked"] == nq
