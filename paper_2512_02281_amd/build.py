@@ -10,7 +10,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libtrinity_ivf.so")
-SOURCES = ["tri_api.hip", "coarse.hip", "scan.hip", "select.hip", "pack.hip", "build_kernels.hip", "feedback.hip", "graph_engine.hip", "probe.hip"]
+SOURCES = ["tri_api.hip", "coarse.hip", "scan.hip", "select.hip", "pack.hip", "build_kernels.hip", "feedback.hip", "graph_engine.hip", "pq_engine.hip", "probe.hip"]
 FLAGS = ["-O3", "--offload-arch=gfx950", "-fPIC", "-std=c++17", "-Wall", "-Wno-unused-function",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
 
@@ -28,6 +28,7 @@ def build_library(force: bool = False, verbose: bool = False) -> str:
     headers = [os.path.join(CSRC, f) for f in os.listdir(CSRC) if f.endswith(".h")]
     headers.append(os.path.join(os.path.dirname(HERE), "include", "trinity_ivf.h"))
     headers.append(os.path.join(os.path.dirname(HERE), "include", "trinity_graph.h"))
+    headers.append(os.path.join(os.path.dirname(HERE), "include", "trinity_pq.h"))
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 
     def compile_one(src: str) -> str:

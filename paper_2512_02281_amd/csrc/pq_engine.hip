@@ -1,0 +1,491 @@
+// IVF search over product-quantised lists (the compressed variant of the inverted-file index named in the
+// paper's Sec. 1), on top of a resident IVF index: that index's centroids and lists choose a query's candidates,
+// what is scored are m-byte codes, by summing one table entry per sub-space.
+//
+// Build: codebooks (given, or Lloyd per sub-space on a sample of the stored vectors), then every stored vector is
+// encoded, list-major.  Search, per batch of queries with one k, nprobe and metric:
+//   1. the query rows are copied into zero-padded rows of the index's row length;
+//   2. coarse scores against the centroids: the same matrix-core contraction the IVF-Flat pool uses;
+//   3. the nprobe best lists per query (one workgroup per query, streaming selection, see PqCollector);
+//   4. the query's tables, m x 256 fp32 partial scores (values where smaller is better: the negative partial
+//      products for the inner product);
+//   5. one workgroup per query: tables into LDS, the codes of its probed lists streamed once (m bytes per vector,
+//      one vector per thread and round), m LDS look-ups summed in sub-space order, the k best by (score, id) kept
+//      by the same streaming selection.
+// Bound of step 5: LDS look-ups (m per vector and query, 4 bytes each, random banks); the codes themselves are
+// 1/16 of the fp16 rows and mostly cache-resident.
+#include "../../include/trinity_pq.h"
+#include "tri_common.h"
+
+#include <algorithm>
+#include <new>
+#include <vector>
+
+namespace {
+
+#define PQ_TRY(expr)                                                                           \
+    do {                                                                                       \
+        hipError_t e_ = (expr);                                                                \
+        if (e_ != hipSuccess) return tri_fail(TRI_EHIP, "%s -> %s", #expr, hipGetErrorString(e_)); \
+    } while (0)
+
+constexpr uint32_t PQ_THREADS = 256;
+constexpr uint32_t PQ_BUF = 4096;         // composites the streaming selection holds in LDS (32 KB)
+
+size_t up256(size_t x) { return (x + 255) / 256 * 256; }
+
+__device__ __forceinline__ float pq_elem(const uint8_t *row, uint32_t i, uint32_t dtype)
+{
+    return dtype == 1u ? (float)((const _Float16 *)row)[i] : ((const float *)row)[i];
+}
+
+// ---------------------------------------------------------------------------------------- build
+// Stored position of training row r: every stride-th stored vector.
+__global__ void pq_init_kernel(const uint8_t *__restrict__ vecs, uint32_t row_bytes, uint32_t dtype, uint64_t n,
+                               uint32_t m, uint32_t dsub, uint64_t seed, float *__restrict__ cb)
+{
+    // entry c of every sub-space starts as the sub-vector of one stored vector: 256 positions spread over the
+    // index, shifted by the seed
+    const uint32_t c = blockIdx.x;
+    const uint64_t step = n / TRI_PQ_KSUB;               // (n >= 256: at least 1)
+    const uint64_t pos = ((uint64_t)c * step + seed % step) % n;
+    for (uint32_t j = threadIdx.x; j < m * dsub; j += blockDim.x) {      // j over the dim values
+        const uint32_t mm = j / dsub, e = j % dsub;
+        cb[((size_t)mm * TRI_PQ_KSUB + c) * dsub + e] = pq_elem(vecs + pos * row_bytes, j, dtype);
+    }
+}
+
+// Nearest entry of sub-space mm's codebook (in LDS) to the sub-vector x: squared L2 accumulated in coordinate
+// order, ties to the smaller number.
+template <int DSUB_MAX>
+__device__ __forceinline__ uint32_t pq_nearest(const float *cb_lds, const float (&x)[DSUB_MAX], uint32_t dsub)
+{
+    float best = INFINITY;
+    uint32_t arg = 0;
+    for (uint32_t c = 0; c < TRI_PQ_KSUB; ++c) {
+        float d2 = 0.f;
+        for (uint32_t e = 0; e < dsub; ++e) {
+            const float d = x[e] - cb_lds[c * dsub + e];
+            d2 = __builtin_fmaf(d, d, d2);
+        }
+        if (d2 < best) {
+            best = d2;
+            arg = c;
+        }
+    }
+    return arg;
+}
+
+// grid (rows / 256, m): one thread per (row, sub-space); the sub-space's codebook sits in LDS.
+// TRAIN: rows are the training sample (every stride-th stored vector), the sub-vector is added to its cell's sum;
+// otherwise all stored vectors, the code is written.
+template <bool TRAIN>
+__global__ __launch_bounds__(PQ_THREADS) void pq_assign_kernel(const uint8_t *__restrict__ vecs, uint32_t row_bytes,
+                                                               uint32_t dtype, uint64_t rows, uint64_t stride, uint32_t m,
+                                                               uint32_t dsub, const float *__restrict__ cb,
+                                                               float *__restrict__ sums, uint32_t *__restrict__ counts,
+                                                               uint8_t *__restrict__ codes)
+{
+    extern __shared__ float cb_lds[];
+    const uint32_t mm = blockIdx.y;
+    for (uint32_t i = threadIdx.x; i < TRI_PQ_KSUB * dsub; i += PQ_THREADS) cb_lds[i] = cb[(size_t)mm * TRI_PQ_KSUB * dsub + i];
+    __syncthreads();
+    const uint64_t r = (uint64_t)blockIdx.x * PQ_THREADS + threadIdx.x;
+    if (r >= rows) return;
+    const uint64_t pos = r * stride;
+    float x[TRI_PQ_DSUB_MAX];
+    for (uint32_t e = 0; e < dsub; ++e) x[e] = pq_elem(vecs + pos * row_bytes, mm * dsub + e, dtype);
+    const uint32_t c = pq_nearest<TRI_PQ_DSUB_MAX>(cb_lds, x, dsub);
+    if (TRAIN) {
+        float *to = sums + ((size_t)mm * TRI_PQ_KSUB + c) * dsub;
+        for (uint32_t e = 0; e < dsub; ++e) atomicAdd(&to[e], x[e]);
+        atomicAdd(&counts[mm * TRI_PQ_KSUB + c], 1u);
+    } else {
+        codes[pos * m + mm] = (uint8_t)c;
+    }
+}
+
+__global__ void pq_update_kernel(uint32_t total, uint32_t dsub, const float *__restrict__ sums,
+                                 const uint32_t *__restrict__ counts, float *__restrict__ cb)
+{
+    const uint32_t i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= total) return;
+    const uint32_t cnt = counts[i / dsub];
+    if (cnt) cb[i] = sums[i] / (float)cnt;          // (a cell nothing is nearest to keeps its entry)
+}
+
+// ---------------------------------------------------------------------------------------- search
+__global__ void pq_pad_queries_kernel(const uint8_t *__restrict__ q, size_t pitch, uint32_t nq, uint32_t dim_bytes,
+                                      uint32_t row_bytes, uint8_t *__restrict__ rows)
+{
+    const uint32_t r = blockIdx.x;
+    for (uint32_t b = threadIdx.x; b < row_bytes; b += blockDim.x) rows[(size_t)r * row_bytes + b] = b < dim_bytes ? q[r * pitch + b] : 0;
+}
+
+// Streaming selection of the k smallest 64-bit composites (score key << 32 | id) offered to a workgroup: the
+// current best (at most k, sorted) head an LDS array, offers that beat the k-th are appended behind them, and when
+// the array could not take another round of offers it is sorted and cut back to k.  Exact: an offer is dropped only
+// when k composites smaller than it are known.
+struct PqCollector {
+    uint64_t buf[PQ_BUF];
+    uint32_t count;        // composites in buf
+    uint32_t have;         // of which sorted best (the first `have`)
+    uint64_t bound;        // the k-th best when have == k, else all-ones
+};
+
+// Bitonic sort of buf[0..n) ascending (n <= PQ_BUF, padded with all-ones to a power of two); all threads.
+__device__ void pq_sort(uint64_t *a, uint32_t n)
+{
+    uint32_t np2 = 1;
+    while (np2 < n) np2 <<= 1;
+    for (uint32_t i = n + threadIdx.x; i < np2; i += PQ_THREADS) a[i] = ~0ull;
+    __syncthreads();
+    for (uint32_t size = 2; size <= np2; size <<= 1)
+        for (uint32_t stride = size >> 1; stride > 0; stride >>= 1) {
+            for (uint32_t i = threadIdx.x; i < np2 / 2; i += PQ_THREADS) {
+                const uint32_t lo = 2 * i - (i & (stride - 1)), hi = lo + stride;
+                const bool up = (lo & size) == 0;
+                const uint64_t x = a[lo], y = a[hi];
+                if ((x > y) == up) {
+                    a[lo] = y;
+                    a[hi] = x;
+                }
+            }
+            __syncthreads();
+        }
+}
+
+__device__ __forceinline__ void pq_collect_init(PqCollector &c)
+{
+    if (threadIdx.x == 0) {
+        c.count = 0;
+        c.have = 0;
+        c.bound = ~0ull;
+    }
+    __syncthreads();
+}
+
+// Sort what was collected and keep the k best.  All threads; ends with a barrier.
+__device__ void pq_collect_settle(PqCollector &c, uint32_t k)
+{
+    __syncthreads();
+    const uint32_t n = c.count;
+    pq_sort(c.buf, n);
+    if (threadIdx.x == 0) {
+        c.have = n < k ? n : k;
+        c.count = c.have;
+        c.bound = c.have == k ? c.buf[k - 1] : ~0ull;
+    }
+    __syncthreads();
+}
+
+// One round of offers: every thread may offer one composite (valid = it has one).  All threads call it together.
+// Whether the array could take another round is decided by all threads as one: the barrier that ends the round also
+// combines what each thread saw of the counter after its own append (the thread that appended last saw them all).
+__device__ __forceinline__ void pq_collect_round(PqCollector &c, uint32_t k, bool valid, uint64_t comp)
+{
+    if (valid && comp < c.bound) c.buf[atomicAdd(&c.count, 1u)] = comp;
+    if (__syncthreads_or(c.count + PQ_THREADS > PQ_BUF)) pq_collect_settle(c, k);
+}
+
+// (3) the nprobe best lists of each query: best first, ties to the smaller list number.
+__global__ __launch_bounds__(PQ_THREADS) void pq_probe_kernel(const float *__restrict__ scores, uint32_t ldc, uint32_t nlist,
+                                                              uint32_t nprobe, uint32_t metric, uint32_t *__restrict__ probes)
+{
+    __shared__ PqCollector col;
+    const float *row = scores + (size_t)blockIdx.x * ldc;
+    pq_collect_init(col);
+    for (uint32_t i0 = 0; i0 < nlist; i0 += PQ_THREADS) {
+        const uint32_t i = i0 + threadIdx.x;
+        const bool valid = i < nlist;
+        const uint64_t comp = valid ? ((uint64_t)tri_score_key(row[i], metric == 1u ? 1u : 0u) << 32) | i : ~0ull;
+        pq_collect_round(col, nprobe, valid, comp);
+    }
+    pq_collect_settle(col, nprobe);
+    for (uint32_t i = threadIdx.x; i < nprobe; i += PQ_THREADS)
+        probes[(size_t)blockIdx.x * nprobe + i] = i < col.have ? (uint32_t)(col.buf[i] & 0xFFFFFFFFu) : 0xFFFFFFFFu;
+}
+
+// (4) tables: lut[q][mm][c] = sum over the sub-space of (q - entry)^2, or of -q * entry, in coordinate order.
+__global__ __launch_bounds__(PQ_THREADS) void pq_lut_kernel(const uint8_t *__restrict__ qrows, uint32_t row_bytes, uint32_t dtype,
+                                                            uint32_t m, uint32_t dsub, uint32_t metric,
+                                                            const float *__restrict__ cb, float *__restrict__ lut)
+{
+    const uint32_t q = blockIdx.x;
+    const uint8_t *row = qrows + (size_t)q * row_bytes;
+    for (uint32_t t = threadIdx.x; t < m * TRI_PQ_KSUB; t += PQ_THREADS) {
+        const uint32_t mm = t / TRI_PQ_KSUB;
+        const float *entry = cb + (size_t)t * dsub;
+        float acc = 0.f;
+        for (uint32_t e = 0; e < dsub; ++e) {
+            const float x = pq_elem(row, mm * dsub + e, dtype);
+            if (metric == 0u) {
+                const float d = x - entry[e];
+                acc = __builtin_fmaf(d, d, acc);
+            } else {
+                acc = __builtin_fmaf(-x, entry[e], acc);
+            }
+        }
+        lut[(size_t)q * m * TRI_PQ_KSUB + t] = acc;
+    }
+}
+
+// (5) one workgroup per query.
+__global__ __launch_bounds__(PQ_THREADS) void pq_scan_kernel(const float *__restrict__ lut, uint32_t m,
+                                                             const uint32_t *__restrict__ probes, uint32_t nprobe,
+                                                             const uint32_t *__restrict__ list_off, const uint32_t *__restrict__ ids,
+                                                             const uint8_t *__restrict__ codes, uint32_t k, uint32_t metric,
+                                                             uint32_t *__restrict__ ids_out, float *__restrict__ dist_out,
+                                                             uint32_t *__restrict__ n_out)
+{
+    extern __shared__ float lut_lds[];
+    __shared__ PqCollector col;
+    const uint32_t q = blockIdx.x;
+    for (uint32_t t = threadIdx.x; t < m * TRI_PQ_KSUB; t += PQ_THREADS) lut_lds[t] = lut[(size_t)q * m * TRI_PQ_KSUB + t];
+    pq_collect_init(col);
+    const uint32_t words = m / 4;
+    for (uint32_t p = 0; p < nprobe; ++p) {
+        const uint32_t l = probes[(size_t)q * nprobe + p];
+        if (l == 0xFFFFFFFFu) continue;                                      // (uniform)
+        const uint32_t v0 = list_off[l], v1 = list_off[l + 1];
+        for (uint32_t vb = v0; vb < v1; vb += PQ_THREADS) {
+            const uint32_t v = vb + threadIdx.x;
+            const bool valid = v < v1;
+            float sum = 0.f;
+            if (valid) {
+                const uint32_t *code = (const uint32_t *)(codes + (size_t)v * m);
+                for (uint32_t w = 0; w < words; ++w) {
+                    const uint32_t c4 = code[w];
+                    const float *t = lut_lds + (size_t)w * 4 * TRI_PQ_KSUB;
+                    sum += t[c4 & 0xFFu];
+                    sum += t[TRI_PQ_KSUB + ((c4 >> 8) & 0xFFu)];
+                    sum += t[2 * TRI_PQ_KSUB + ((c4 >> 16) & 0xFFu)];
+                    sum += t[3 * TRI_PQ_KSUB + (c4 >> 24)];
+                }
+            }
+            const uint32_t key = tri_score_key(sum, 0u);
+            // (the id is fetched only for a vector whose key alone does not rule it out)
+            const bool maybe = valid && ((uint64_t)key << 32) <= col.bound;
+            const uint64_t comp = maybe ? ((uint64_t)key << 32) | ids[v] : ~0ull;
+            pq_collect_round(col, k, maybe, comp);
+        }
+    }
+    pq_collect_settle(col, k);
+    const uint32_t n = col.have;
+    for (uint32_t i = threadIdx.x; i < k; i += PQ_THREADS) {
+        const bool real = i < n;
+        const float val = real ? tri_key_score((uint32_t)(col.buf[i] >> 32), 0u) : INFINITY;
+        ids_out[(size_t)q * k + i] = real ? (uint32_t)(col.buf[i] & 0xFFFFFFFFu) : 0xFFFFFFFFu;
+        dist_out[(size_t)q * k + i] = metric == 1u ? (real && val == 0.f ? 0.f : -val) : val;
+    }
+    if (threadIdx.x == 0) n_out[q] = n;
+}
+
+}  // namespace
+
+struct tri_pq {
+    const tri_index *index = nullptr;
+    TriIndexView view{};
+    pq_params p{};
+    uint32_t dsub = 0;
+    float *cb = nullptr;        // [m][256][dsub]
+    uint8_t *codes = nullptr;   // [n][m], list-major
+};
+
+namespace {
+
+int pq_check(const TriIndexView &v, const pq_params *p, uint32_t *dsub)
+{
+    if (!p) return tri_fail(TRI_EINVAL, "params is NULL");
+    const uint32_t dim = v.dev.dim;
+    if (p->m == 0 || p->m % 4 != 0 || dim % p->m != 0)
+        return tri_fail(TRI_EINVAL, "m = %u must be a multiple of 4 that divides dim = %u", p->m, dim);
+    if (dim / p->m > TRI_PQ_DSUB_MAX) return tri_fail(TRI_EINVAL, "dim / m = %u exceeds %u", dim / p->m, TRI_PQ_DSUB_MAX);
+    if ((size_t)p->m * TRI_PQ_KSUB * 4 + sizeof(PqCollector) + 1024 > 160u * 1024u)
+        return tri_fail(TRI_EINVAL, "m = %u: the tables of a query (%u KiB) do not fit the LDS beside the selection buffer",
+                        p->m, p->m * TRI_PQ_KSUB * 4 / 1024);
+    if (v.n < TRI_PQ_KSUB) return tri_fail(TRI_EINVAL, "the index holds %llu vectors, fewer than a codebook has entries", (unsigned long long)v.n);
+    *dsub = dim / p->m;
+    return TRI_OK;
+}
+
+}  // namespace
+
+extern "C" int pq_build_bytes(const tri_index *index, const pq_params *p, size_t *dev_bytes, size_t *tmp_bytes)
+{
+    if (!index || !dev_bytes || !tmp_bytes) return tri_fail(TRI_EINVAL, "NULL argument");
+    TriIndexView v;
+    tri_index_view(index, &v);
+    uint32_t dsub = 0;
+    const int rc = pq_check(v, p, &dsub);
+    if (rc) return rc;
+    *dev_bytes = up256((size_t)p->m * TRI_PQ_KSUB * dsub * 4) + up256((size_t)v.n * p->m);
+    *tmp_bytes = up256((size_t)p->m * TRI_PQ_KSUB * dsub * 4) + up256((size_t)p->m * TRI_PQ_KSUB * 4);
+    return TRI_OK;
+}
+
+extern "C" int pq_build(const tri_index *index, const pq_params *p, const float *codebooks, void *dev_mem, size_t dev_mem_bytes,
+                        void *tmp_dev, size_t tmp_bytes, tri_pq **out)
+{
+    if (!index || !dev_mem || !out) return tri_fail(TRI_EINVAL, "NULL argument");
+    size_t need = 0, tmp_need = 0;
+    int rc = pq_build_bytes(index, p, &need, &tmp_need);
+    if (rc) return rc;
+    if ((uintptr_t)dev_mem % 256 || (tmp_dev && (uintptr_t)tmp_dev % 256)) return tri_fail(TRI_EINVAL, "dev_mem and tmp_dev must be 256-byte aligned");
+    if (dev_mem_bytes < need) return tri_fail(TRI_ENOMEM, "dev_mem has %zu bytes, %zu needed", dev_mem_bytes, need);
+    if (!codebooks && (!tmp_dev || tmp_bytes < tmp_need)) return tri_fail(TRI_ENOMEM, "tmp_dev has %zu bytes, %zu needed to train the codebooks", tmp_bytes, tmp_need);
+    tri_pq *Q = new (std::nothrow) tri_pq();
+    if (!Q) return tri_fail(TRI_ENOMEM, "out of host memory");
+    Q->index = index;
+    tri_index_view(index, &Q->view);
+    Q->p = *p;
+    Q->dsub = Q->view.dev.dim / p->m;
+    const TriIndexView &v = Q->view;
+    const uint32_t m = p->m, dsub = Q->dsub;
+    const size_t cb_bytes = (size_t)m * TRI_PQ_KSUB * dsub * 4;
+    Q->cb = (float *)dev_mem;
+    Q->codes = (uint8_t *)dev_mem + up256(cb_bytes);
+    hipStream_t s = v.stream;
+    auto fail = [&](int code) { delete Q; return code; };
+#define PQ_TRY_B(expr)                                                                                         \
+    do {                                                                                                       \
+        hipError_t e_ = (expr);                                                                                \
+        if (e_ != hipSuccess) return fail(tri_fail(TRI_EHIP, "%s -> %s", #expr, hipGetErrorString(e_)));       \
+    } while (0)
+    PQ_TRY_B(hipSetDevice(v.device));
+    PQ_TRY_B(hipStreamSynchronize(s));
+    const uint32_t lds = TRI_PQ_KSUB * dsub * 4;
+    if (codebooks) {
+        PQ_TRY_B(hipMemcpyAsync(Q->cb, codebooks, cb_bytes, hipMemcpyHostToDevice, s));
+    } else {
+        float *sums = (float *)tmp_dev;
+        uint32_t *counts = (uint32_t *)((uint8_t *)tmp_dev + up256(cb_bytes));
+        uint64_t rows = p->train_rows ? p->train_rows : 65536;
+        rows = std::min<uint64_t>(rows, v.n);
+        const uint64_t stride = v.n / rows;
+        hipLaunchKernelGGL(pq_init_kernel, dim3(TRI_PQ_KSUB), dim3(1024), 0, s, (const uint8_t *)v.dev.vecs, v.dev.row_bytes,
+                           v.dev.dtype, v.n, m, dsub, p->seed, Q->cb);
+        PQ_TRY_B(hipGetLastError());
+        for (uint32_t it = 0; it < p->train_iters; ++it) {
+            PQ_TRY_B(tri_launch_fill_u32(s, (uint32_t *)sums, 0u, cb_bytes / 4));
+            PQ_TRY_B(tri_launch_fill_u32(s, counts, 0u, (size_t)m * TRI_PQ_KSUB));
+            hipLaunchKernelGGL(pq_assign_kernel<true>, dim3((unsigned)((rows + PQ_THREADS - 1) / PQ_THREADS), m), dim3(PQ_THREADS), lds, s,
+                               (const uint8_t *)v.dev.vecs, v.dev.row_bytes, v.dev.dtype, rows, stride, m, dsub, Q->cb, sums, counts,
+                               (uint8_t *)nullptr);
+            PQ_TRY_B(hipGetLastError());
+            const uint32_t total = m * TRI_PQ_KSUB * dsub;
+            hipLaunchKernelGGL(pq_update_kernel, dim3((total + 255) / 256), dim3(256), 0, s, total, dsub, sums, counts, Q->cb);
+            PQ_TRY_B(hipGetLastError());
+        }
+    }
+    hipLaunchKernelGGL(pq_assign_kernel<false>, dim3((unsigned)((v.n + PQ_THREADS - 1) / PQ_THREADS), m), dim3(PQ_THREADS), lds, s,
+                       (const uint8_t *)v.dev.vecs, v.dev.row_bytes, v.dev.dtype, v.n, (uint64_t)1, m, dsub, Q->cb, (float *)nullptr,
+                       (uint32_t *)nullptr, Q->codes);
+    PQ_TRY_B(hipGetLastError());
+    PQ_TRY_B(hipStreamSynchronize(s));
+#undef PQ_TRY_B
+    *out = Q;
+    return TRI_OK;
+}
+
+extern "C" int pq_destroy(tri_pq *pq)
+{
+    if (!pq) return TRI_OK;
+    (void)hipSetDevice(pq->view.device);
+    (void)hipStreamSynchronize(pq->view.stream);
+    delete pq;
+    return TRI_OK;
+}
+
+extern "C" int pq_export(const tri_pq *pq, float *codebooks, uint8_t *codes)
+{
+    if (!pq) return tri_fail(TRI_EINVAL, "pq is NULL");
+    PQ_TRY(hipSetDevice(pq->view.device));
+    PQ_TRY(hipStreamSynchronize(pq->view.stream));
+    if (codebooks) PQ_TRY(hipMemcpy(codebooks, pq->cb, (size_t)pq->p.m * TRI_PQ_KSUB * pq->dsub * 4, hipMemcpyDeviceToHost));
+    if (codes) PQ_TRY(hipMemcpy(codes, pq->codes, (size_t)pq->view.n * pq->p.m, hipMemcpyDeviceToHost));
+    return TRI_OK;
+}
+
+namespace {
+
+struct PqWs {
+    uint8_t *qrows;
+    float *scores;
+    uint32_t *probes;
+    float *lut;
+    size_t total;
+};
+
+PqWs pq_carve(const tri_pq *pq, uint32_t nq, uint8_t *base)
+{
+    const TriIndexDev &d = pq->view.dev;
+    const uint32_t ldc = (d.nlist + 31u) / 32u * 32u;
+    size_t off = 0;
+    auto take = [&](size_t bytes) { uint8_t *p = base ? base + off : nullptr; off += up256(bytes); return p; };
+    PqWs w;
+    w.qrows = take((size_t)nq * d.row_bytes);
+    w.scores = (float *)take((size_t)nq * ldc * 4);
+    w.probes = (uint32_t *)take((size_t)nq * TRI_PQ_NPROBE_MAX * 4);
+    w.lut = (float *)take((size_t)nq * pq->p.m * TRI_PQ_KSUB * 4);
+    w.total = off;
+    return w;
+}
+
+}  // namespace
+
+extern "C" int pq_search_bytes(const tri_pq *pq, uint32_t nq, size_t *ws_bytes)
+{
+    if (!pq || !ws_bytes) return tri_fail(TRI_EINVAL, "NULL argument");
+    if (nq == 0) return tri_fail(TRI_EINVAL, "nq must be at least 1");
+    *ws_bytes = pq_carve(pq, nq, nullptr).total;
+    return TRI_OK;
+}
+
+extern "C" int pq_search_batch(tri_pq *pq, const void *queries, size_t pitch_bytes, uint32_t nq, uint32_t k, uint32_t nprobe,
+                               uint32_t metric, void *ws, size_t ws_bytes, uint32_t *ids_out, float *dist_out, uint32_t *n_out,
+                               uint32_t *probes_out)
+{
+    if (!pq || !queries || !ws || !ids_out || !dist_out || !n_out) return tri_fail(TRI_EINVAL, "NULL argument");
+    const TriIndexDev &d = pq->view.dev;
+    const uint32_t es = d.dtype == 1u ? 2u : 4u;
+    if (nq == 0) return TRI_OK;
+    if (k == 0 || k > TRI_PQ_KMAX) return tri_fail(TRI_EINVAL, "k must be 1..%u", TRI_PQ_KMAX);
+    if (nprobe == 0 || nprobe > TRI_PQ_NPROBE_MAX || nprobe > d.nlist) return tri_fail(TRI_EINVAL, "nprobe must be 1..min(nlist, %u)", TRI_PQ_NPROBE_MAX);
+    if (metric != TRI_L2 && metric != TRI_IP) return tri_fail(TRI_EINVAL, "metric must be TRI_L2 or TRI_IP");
+    if (pitch_bytes < (size_t)d.dim * es) return tri_fail(TRI_EINVAL, "pitch_bytes %zu is shorter than a query row (%u bytes)", pitch_bytes, d.dim * es);
+    if ((uintptr_t)ws % 256) return tri_fail(TRI_EINVAL, "ws must be 256-byte aligned");
+    const PqWs w = pq_carve(pq, nq, (uint8_t *)ws);
+    if (ws_bytes < w.total) return tri_fail(TRI_ENOMEM, "ws has %zu bytes, %zu needed", ws_bytes, w.total);
+    PQ_TRY(hipSetDevice(pq->view.device));
+    hipStream_t s = pq->view.stream;
+    const uint32_t m = pq->p.m, ldc = (d.nlist + 31u) / 32u * 32u;
+    const uint32_t lut_bytes = m * TRI_PQ_KSUB * 4;
+    static uint32_t lds_limit = 0;          // (more LDS than a kernel gets by default: raised once per growth)
+    if (lut_bytes > lds_limit) {
+        PQ_TRY(hipFuncSetAttribute((const void *)pq_scan_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lut_bytes));
+        lds_limit = lut_bytes;
+    }
+    hipLaunchKernelGGL(pq_pad_queries_kernel, dim3(nq), dim3(256), 0, s, (const uint8_t *)queries, pitch_bytes, nq, d.dim * es,
+                       d.row_bytes, w.qrows);
+    PQ_TRY(hipGetLastError());
+    PQ_TRY(tri_launch_coarse_gemm(s, d.dtype == 1u ? 1 : 0, w.qrows, d.row_bytes, nq, d.centroids, d.cnorm, d.nlist, d.row_bytes,
+                                  nullptr, 0u, metric, w.scores, ldc));
+    uint32_t *probes = probes_out ? probes_out : w.probes;
+    hipLaunchKernelGGL(pq_probe_kernel, dim3(nq), dim3(PQ_THREADS), 0, s, w.scores, ldc, d.nlist, nprobe, metric, probes);
+    PQ_TRY(hipGetLastError());
+    hipLaunchKernelGGL(pq_lut_kernel, dim3(nq), dim3(PQ_THREADS), 0, s, w.qrows, d.row_bytes, d.dtype, m, pq->dsub, metric, pq->cb, w.lut);
+    PQ_TRY(hipGetLastError());
+    hipLaunchKernelGGL(pq_scan_kernel, dim3(nq), dim3(PQ_THREADS), lut_bytes, s, w.lut, m, probes, nprobe, d.list_off, d.ids, pq->codes,
+                       k, metric, ids_out, dist_out, n_out);
+    PQ_TRY(hipGetLastError());
+    return TRI_OK;
+}
+
+extern "C" int pq_sync(tri_pq *pq)
+{
+    if (!pq) return tri_fail(TRI_EINVAL, "pq is NULL");
+    PQ_TRY(hipSetDevice(pq->view.device));
+    PQ_TRY(hipStreamSynchronize(pq->view.stream));
+    return TRI_OK;
+}

@@ -132,6 +132,8 @@ struct tri_index {
     std::vector<uint32_t> list_len;   // host copy of the list lengths
 };
 
+void tri_index_view(const tri_index *ix, TriIndexView *out);
+
 struct tri_pool {
     tri_pool_cfg cfg{};
     int device = 0;
@@ -955,6 +957,14 @@ extern "C" int ivf_build(tri_pool *P, const ivf_params *p, const void *base, uin
     drop_graphs(P);                    // (recorded steps cover the indexes attached when they were recorded)
     *out = ix;
     return TRI_OK;
+}
+
+void tri_index_view(const tri_index *ix, TriIndexView *out)
+{
+    out->dev = ix->dev;
+    out->stream = ix->pool->stream;
+    out->device = ix->pool->device;
+    out->n = ix->n;
 }
 
 extern "C" int ivf_export(const tri_index *ix, float *centroids, uint64_t *list_off, int64_t *list_ids)

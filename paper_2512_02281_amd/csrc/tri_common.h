@@ -189,6 +189,16 @@ struct TriLaunchCtx {
     uint32_t S, W, kmax, nprobe_max, max_total_lists, slot_row_bytes, n_cu;
 };
 
+// What another engine of the library needs to know of a resident index (tri_api.hip owns the object).
+struct tri_index;
+struct TriIndexView {
+    TriIndexDev dev;
+    hipStream_t stream;       // of the pool the index is attached to
+    int device;
+    uint64_t n;
+};
+void tri_index_view(const tri_index *ix, TriIndexView *out);
+
 // Record the thread's last error text (what tri_last_error() returns) and hand back `code`.
 int tri_fail(int code, const char *fmt, ...) __attribute__((format(printf, 2, 3)));
 

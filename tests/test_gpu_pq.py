@@ -1,0 +1,185 @@
+"""GPU parity of IVF search over product-quantised lists (include/trinity_pq.h) against oracle/pq.py, through the C ABI."""
+import ctypes
+
+import numpy as np
+import pytest
+
+import oracle
+from oracle import pq as opq
+from tests import checker, harness
+
+pytestmark = pytest.mark.gpu
+
+
+def _say(msg):
+    harness.say(msg)
+
+
+def _setup(tri, dtype, n, d, nlist, seed, integer=False):
+    import torch
+    rng = np.random.default_rng(seed)
+    np_dtype = np.float32 if dtype == "f32" else np.float16
+    centres = rng.normal(0.0, 1.0, size=(nlist, d))
+    base = centres[rng.integers(0, nlist, n)] + rng.normal(0.0, 0.4, size=(n, d))
+    if integer:
+        base = np.round(base * 4.0)
+    base = base.astype(np_dtype)
+    init = base[rng.choice(n, nlist, replace=False)].astype(np.float32)
+    pool = harness.default_pool(tri, slots=16, max_dim=d, max_nlist=nlist, max_total_lists=nlist)
+    idx = pool.build_index(base, d, nlist, tri.TRI_F32 if dtype == "f32" else tri.TRI_F16, tri.TRI_L2, 3, centroids=init)
+    oidx = harness.oracle_index(tri, idx, base)
+    return rng, base, pool, idx, oidx, torch
+
+
+def _to_host(ids, dist, n_out, probes):
+    ids = ids.cpu().numpy().view(np.uint32).astype(np.int64)
+    ids[ids == 0xFFFFFFFF] = -1
+    return ids, dist.cpu().numpy(), n_out.cpu().numpy().astype(np.int64), probes.cpu().numpy().view(np.uint32)
+
+
+def _compare(oidx, codes_lm, cb, queries, k, nprobe, metric, ids, dist, n_out, probes, tol, strict=False):
+    """Every query through the tie-aware checker, with the oracle's scores of ALL candidates of the probed lists."""
+    n, d = oidx.n, oidx.d
+    xhat = np.empty((n, d), dtype=np.float64)
+    xhat[oidx.list_ids] = opq.decode(codes_lm, cb)
+    report = dict(checked=0, coarse_near_tie=0, tie_positions=0)
+    for i in range(queries.shape[0]):
+        q = queries[i]
+        coarse = oracle.coarse_scores(oidx, q, metric)
+        want_probe = oracle.probe_set(coarse, nprobe, metric)
+        got_probe = probes[i]
+        assert len(set(got_probe.tolist())) == nprobe
+        use = want_probe
+        if set(got_probe.tolist()) != set(want_probe.tolist()):
+            qn2 = float((q.astype(np.float64) ** 2).sum())
+            cn2 = float((oidx.centroids.astype(np.float64) ** 2).sum(axis=1).max())
+            eps = checker.ABS_EPS * (qn2 + cn2 if metric == 0 else np.sqrt(qn2 * cn2))
+            assert checker.probe_sets_equivalent(got_probe, want_probe, coarse, metric, checker.tolerance_for(oidx.dtype), eps), \
+                f"query {i}: probe set differs beyond a boundary near-tie"
+            report["coarse_near_tie"] += 1
+            use = got_probe
+        _, _, _, _, cand_ids, cand_sc = opq.search(oidx, codes_lm, cb, q, k, nprobe, metric, probe=use, all_candidates=True)
+        report["tie_positions"] += checker.check_result(q, xhat, metric, k, ids[i, :k], dist[i, :k], int(n_out[i]), cand_ids, cand_sc,
+                                                        0.0 if strict else tol, strict=strict)
+        report["checked"] += 1
+    return report
+
+
+@pytest.mark.parametrize("dtype,d,m", [("f16", 768, 96), ("f32", 128, 16), ("f16", 320, 20)])
+def test_codebooks_codes_and_search_against_the_oracle(dtype, d, m):
+    """Trained codebooks are exported and handed to the oracle; the library's codes must be the oracle's (nearest
+    entry, ties to the smaller number; a code may differ only where two entries are equally near to rounding), the
+    training must not be worse than the oracle's Lloyd from the same start, and the search results must pass the
+    tie-aware checker with the oracle's scores of every candidate."""
+    tri = harness.lib()
+    from paper_2512_02281_amd import pq as tpq
+    n, nlist = 16_000, 24
+    rng, base, pool, idx, oidx, torch = _setup(tri, dtype, n, d, nlist, seed=500 + d)
+    with pool:
+        X_lm = base[oidx.list_ids].astype(np.float64)
+        with tpq.PQ(pool, idx, m, train_iters=0, seed=3) as start:
+            cb0, _ = start.export(n, d)
+        with tpq.PQ(pool, idx, m, train_iters=6, train_rows=4000, seed=3) as pq:
+            cb, codes = pq.export(n, d)
+            assert np.all(np.isfinite(cb))
+            # codes: the oracle's, except where the runner-up is as near to rounding
+            want = opq.encode(X_lm, cb)
+            diff = np.argwhere(want != codes)
+            w = d // m
+            for r, mm in diff[:2000]:
+                sub = X_lm[r, mm * w:(mm + 1) * w]
+                d_got = ((sub - cb[mm, codes[r, mm]]) ** 2).sum()
+                d_best = ((sub - cb[mm, want[r, mm]]) ** 2).sum()
+                assert d_got <= d_best * (1 + 1e-5) + 1e-9, f"row {r} sub-space {mm}: code {codes[r, mm]} is not a nearest entry"
+            # training: the sample is every n/4000-th stored vector; fp64 Lloyd from the same start
+            sample = X_lm[::n // 4000][:4000]
+            cb_oracle = opq.train(sample, cb0, 6)
+            err_gpu = opq.quantisation_error(X_lm, codes, cb)
+            err_oracle = opq.quantisation_error(X_lm, opq.encode(X_lm, cb_oracle), cb_oracle)
+            err_start = opq.quantisation_error(X_lm, opq.encode(X_lm, cb0), cb0)
+            _say(f"pq {dtype} d={d} m={m}: {diff.shape[0]} of {n * m} codes differ from the oracle's (near-ties); quantisation error "
+                 f"start {err_start:.4f} -> gpu {err_gpu:.4f}, oracle's Lloyd {err_oracle:.4f}")
+            assert diff.shape[0] <= n * m * 1e-3
+            assert err_gpu < err_start and err_gpu <= err_oracle * 1.02
+            # search
+            nq = 40
+            queries = np.ascontiguousarray((base[rng.choice(n, nq)].astype(np.float64) + rng.normal(0, 0.3, size=(nq, d))).astype(base.dtype))
+            qt = torch.from_numpy(queries).cuda()
+            tol = 2e-4
+            for k, nprobe, metric in [(10, 4, 0), (100, 8, 1), (1, 1, 0), (256, nlist, 1)]:
+                ids, dist, n_out, probes = _to_host(*pq.search(qt, k, nprobe, metric))
+                pq.sync()
+                ids, dist, n_out, probes = _to_host(*pq.search(qt, k, nprobe, metric))    # (a second call reuses nothing stale)
+                pq.sync()
+                rep = _compare(oidx, codes, cb, queries, k, nprobe, metric, ids, dist, n_out, probes, tol)
+                _say(f"pq {dtype} d={d}: k={k} nprobe={nprobe} metric={metric} parity {rep}")
+                assert rep["checked"] == nq
+
+
+def test_lossless_codebooks_reproduce_the_flat_search_bit_for_bit():
+    """Integer-valued vectors assembled from integer codebook entries are their own reconstructions and every sum is
+    exact in fp32: the codes must be exactly the oracle's, and ids, order and scores exactly the IVF-Flat oracle's."""
+    tri = harness.lib()
+    from paper_2512_02281_amd import pq as tpq
+    import torch
+    rng = np.random.default_rng(41)
+    m, w, n, nlist = 8, 4, 6000, 10
+    d = m * w
+    cb = np.zeros((m, 256, w), dtype=np.float32)
+    cb[:, :, :] = rng.integers(-6, 7, size=(m, 256, w))
+    src = rng.integers(0, 256, size=(n, m))
+    base = np.concatenate([cb[mm][src[:, mm]] for mm in range(m)], axis=1).astype(np.float32)
+    init = base[rng.choice(n, nlist, replace=False)]
+    with harness.default_pool(tri, slots=16, max_dim=d, max_nlist=nlist, max_total_lists=nlist) as pool:
+        idx = pool.build_index(base, d, nlist, tri.TRI_F32, tri.TRI_L2, 2, centroids=init)
+        oidx = harness.oracle_index(tri, idx, base)
+        with tpq.PQ(pool, idx, m, codebooks=cb) as pq:
+            cb_back, codes = pq.export(n, d)
+            assert np.array_equal(cb_back, cb)
+            assert np.array_equal(codes, opq.encode(base[oidx.list_ids], cb))
+            assert np.array_equal(opq.decode(codes, cb), base[oidx.list_ids].astype(np.float64))
+            queries = rng.integers(-6, 7, size=(30, d)).astype(np.float32)
+            qt = torch.from_numpy(queries).cuda()
+            for k, nprobe, metric in [(10, 3, 0), (50, 10, 1)]:
+                ids, dist, n_out, probes = _to_host(*pq.search(qt, k, nprobe, metric))
+                pq.sync()
+                for i in range(queries.shape[0]):
+                    fp, fids, fdist, fn = oracle.search(oidx, queries[i], k, nprobe, metric)
+                    assert np.array_equal(probes[i], fp) and n_out[i] == fn
+                    assert np.array_equal(ids[i, :k], fids), f"query {i}"
+                    assert np.array_equal(dist[i, :fn].astype(np.float64), fdist[:fn])
+
+
+def test_edge_cases_and_argument_errors():
+    tri = harness.lib()
+    from paper_2512_02281_amd import pq as tpq
+    n, d, nlist, m = 3000, 64, 40, 16
+    rng, base, pool, idx, oidx, torch = _setup(tri, "f32", n, d, nlist, seed=9)
+    with pool:
+        for bad_m in (0, 6, 24, 128):                       # not a multiple of 4, not a divisor of 64, sub-space wider than allowed ...
+            with pytest.raises(tri.TriError) as ei:
+                tpq.PQ(pool, idx, bad_m)
+            assert ei.value.status == tri.TRI_EINVAL
+        with tpq.PQ(pool, idx, m, train_iters=3) as pq:
+            cb, codes = pq.export(n, d)
+            queries = np.ascontiguousarray(base[rng.choice(n, 12)])
+            # rows with a pitch wider than a query, and what lies between them must never be read as data
+            wide = torch.full((12, d + 24), 1e9, dtype=torch.float32, device="cuda")
+            wide[:, :d] = torch.from_numpy(queries).cuda()
+            # k beyond what one short list holds: n_out < k, padded tails
+            ids, dist, n_out, probes = _to_host(*pq.search(wide[:, :d], 256, 1, 0))
+            pq.sync()
+            rep = _compare(oidx, codes, cb, queries, 256, 1, 0, ids, dist, n_out, probes, 2e-4)
+            assert rep["checked"] == 12 and np.any(n_out < 256)
+            ids, dist, n_out, probes = _to_host(*pq.search(wide[:, :d], 5, nlist, 1))           # every list probed
+            pq.sync()
+            _compare(oidx, codes, cb, queries, 5, nlist, 1, ids, dist, n_out, probes, 2e-4)
+            qt = torch.from_numpy(queries).cuda()
+            for k, nprobe, metric in [(0, 1, 0), (257, 1, 0), (5, 0, 0), (5, nlist + 1, 0), (5, 1, 2)]:
+                with pytest.raises(tri.TriError) as ei:
+                    pq.search(qt, k, nprobe, metric)
+                assert ei.value.status == tri.TRI_EINVAL
+            ws_t, ws_bytes = pq.workspace(12)
+            with pytest.raises(tri.TriError) as ei:
+                pq.search(qt, 5, 2, 0, ws=(ws_t, ws_bytes - 256))
+            assert ei.value.status == tri.TRI_ENOMEM

@@ -284,3 +284,34 @@ def test_bench_refuses_more_than_one_gpu():
                        timeout=120)
     assert r.returncode == 2
     assert "ONE GPU" in r.stderr and r.stdout.strip() == ""
+
+
+def test_pq_header_exports_and_layout(tri):
+    """include/trinity_pq.h: every declared function is exported and bound, the parameter struct has the layout the
+    binding assumes (no GPU needed: the calls themselves need a resident index)."""
+    from paper_2512_02281_amd import pq as tpq
+    header = os.path.join(ROOT, "include", "trinity_pq.h")
+    declared = _declared_functions(header)
+    assert sorted(tpq.PQ_EXPORTS) == declared
+    lib = ctypes.CDLL(tri.LIB_PATH)
+    for name in declared:
+        assert hasattr(lib, name), f"{name} is declared in the header but not exported"
+    prog = r'''
+#include <stdio.h>
+#include <stddef.h>
+#include "trinity_pq.h"
+int main(void) {
+  printf("%zu %zu %zu %u %u %u %u\n", sizeof(pq_params), offsetof(pq_params, train_rows), offsetof(pq_params, seed),
+         TRI_PQ_KSUB, TRI_PQ_KMAX, TRI_PQ_NPROBE_MAX, TRI_PQ_DSUB_MAX);
+  return 0;
+}'''
+    with tempfile.TemporaryDirectory() as tmp:
+        src, exe = os.path.join(tmp, "a.c"), os.path.join(tmp, "a.out")
+        open(src, "w").write(prog)
+        subprocess.check_call(["gcc", "-std=c99", "-I", os.path.join(ROOT, "include"), "-o", exe, src])
+        out = [int(v) for v in subprocess.check_output([exe]).decode().split()]
+    assert out == [ctypes.sizeof(tpq.pq_params), tpq.pq_params.train_rows.offset, tpq.pq_params.seed.offset, tpq.TRI_PQ_KSUB,
+                   tpq.TRI_PQ_KMAX, tpq.TRI_PQ_NPROBE_MAX, tpq.TRI_PQ_DSUB_MAX]
+    size = ctypes.c_size_t(0)
+    assert lib.pq_build_bytes(None, None, ctypes.byref(size), ctypes.byref(size)) == tri.TRI_EINVAL
+    assert lib.pq_search_bytes(None, 4, ctypes.byref(size)) == tri.TRI_EINVAL
