@@ -29,10 +29,29 @@ namespace {
         if (e_ != hipSuccess) return tri_fail(TRI_EHIP, "%s -> %s", #expr, hipGetErrorString(e_)); \
     } while (0)
 
-constexpr uint32_t PQ_THREADS = 256;
+constexpr uint32_t PQ_THREADS = 1024;     // a workgroup: 16 wavefronts, so that the LDS look-ups of a compute unit have enough in flight
+constexpr uint32_t PQ_GROUPS_MAX = 8;     // 16-byte groups of a code: m <= 128
 constexpr uint32_t PQ_BUF = 4096;         // composites the streaming selection holds in LDS (32 KB)
 
 size_t up256(size_t x) { return (x + 255) / 256 * 256; }
+
+// Where byte mm of the code of the vector at stored position v lies.  Codes are kept in blocks of 64 consecutive
+// stored positions, transposed: 16-byte group g (sub-spaces 16 g .. 16 g + 15) of the 64 codes side by side (1 KiB),
+// group after group -- so that the 64 lanes of a wavefront, which score 64 consecutive positions, read one contiguous
+// KiB per load instruction instead of 64 pieces m bytes apart, and a code is a handful of 16-byte loads that are all
+// in flight together.  m is padded to a multiple of 16 in this layout (the padding bytes are never looked up).
+__host__ __device__ __forceinline__ uint32_t pq_mpad(uint32_t m) { return (m + 15u) / 16u * 16u; }
+__host__ __device__ __forceinline__ size_t pq_code_at(uint64_t v, uint32_t mm, uint32_t m)
+{
+    return (size_t)(v / 64) * ((size_t)pq_mpad(m) * 64) + (size_t)(mm / 16) * 1024 + (size_t)(v % 64) * 16 + mm % 16;
+}
+
+// Codebooks are kept with the entry number fastest -- cb[(mm * dsub + e) * 256 + c] is coordinate e of entry c of
+// sub-space mm -- so that threads that work on consecutive entries read consecutive words.
+__host__ __device__ __forceinline__ size_t pq_cb_at(uint32_t mm, uint32_t c, uint32_t e, uint32_t dsub)
+{
+    return ((size_t)mm * dsub + e) * TRI_PQ_KSUB + c;
+}
 
 __device__ __forceinline__ float pq_elem(const uint8_t *row, uint32_t i, uint32_t dtype)
 {
@@ -51,7 +70,7 @@ __global__ void pq_init_kernel(const uint8_t *__restrict__ vecs, uint32_t row_by
     const uint64_t pos = ((uint64_t)c * step + seed % step) % n;
     for (uint32_t j = threadIdx.x; j < m * dsub; j += blockDim.x) {      // j over the dim values
         const uint32_t mm = j / dsub, e = j % dsub;
-        cb[((size_t)mm * TRI_PQ_KSUB + c) * dsub + e] = pq_elem(vecs + pos * row_bytes, j, dtype);
+        cb[pq_cb_at(mm, c, e, dsub)] = pq_elem(vecs + pos * row_bytes, j, dtype);
     }
 }
 
@@ -88,7 +107,8 @@ __global__ __launch_bounds__(PQ_THREADS) void pq_assign_kernel(const uint8_t *__
 {
     extern __shared__ float cb_lds[];
     const uint32_t mm = blockIdx.y;
-    for (uint32_t i = threadIdx.x; i < TRI_PQ_KSUB * dsub; i += PQ_THREADS) cb_lds[i] = cb[(size_t)mm * TRI_PQ_KSUB * dsub + i];
+    for (uint32_t i = threadIdx.x; i < TRI_PQ_KSUB * dsub; i += PQ_THREADS)       // i = e * 256 + c in memory -> [c][e] in LDS
+        cb_lds[(i % TRI_PQ_KSUB) * dsub + i / TRI_PQ_KSUB] = cb[(size_t)mm * TRI_PQ_KSUB * dsub + i];
     __syncthreads();
     const uint64_t r = (uint64_t)blockIdx.x * PQ_THREADS + threadIdx.x;
     if (r >= rows) return;
@@ -101,7 +121,7 @@ __global__ __launch_bounds__(PQ_THREADS) void pq_assign_kernel(const uint8_t *__
         for (uint32_t e = 0; e < dsub; ++e) atomicAdd(&to[e], x[e]);
         atomicAdd(&counts[mm * TRI_PQ_KSUB + c], 1u);
     } else {
-        codes[pos * m + mm] = (uint8_t)c;
+        codes[pq_code_at(pos, mm, m)] = (uint8_t)c;
     }
 }
 
@@ -110,8 +130,8 @@ __global__ void pq_update_kernel(uint32_t total, uint32_t dsub, const float *__r
 {
     const uint32_t i = blockIdx.x * blockDim.x + threadIdx.x;
     if (i >= total) return;
-    const uint32_t cnt = counts[i / dsub];
-    if (cnt) cb[i] = sums[i] / (float)cnt;          // (a cell nothing is nearest to keeps its entry)
+    const uint32_t cell = i / dsub, cnt = counts[cell];          // (sums: [sub-space][entry][coordinate])
+    if (cnt) cb[pq_cb_at(cell / TRI_PQ_KSUB, cell % TRI_PQ_KSUB, i % dsub, dsub)] = sums[i] / (float)cnt;   // (a cell nothing is nearest to keeps its entry)
 }
 
 // ---------------------------------------------------------------------------------------- search
@@ -184,8 +204,20 @@ __device__ void pq_collect_settle(PqCollector &c, uint32_t k)
 // combines what each thread saw of the counter after its own append (the thread that appended last saw them all).
 __device__ __forceinline__ void pq_collect_round(PqCollector &c, uint32_t k, bool valid, uint64_t comp)
 {
-    if (valid && comp < c.bound) c.buf[atomicAdd(&c.count, 1u)] = comp;
-    if (__syncthreads_or(c.count + PQ_THREADS > PQ_BUF)) pq_collect_settle(c, k);
+    // one counter update per wavefront, not per lane: before the first bound exists every lane appends
+    const bool push = valid && comp < c.bound;
+    const uint64_t mask = __ballot(push);
+    if (mask) {
+        const uint32_t lane = threadIdx.x & 63;
+        const int leader = __ffsll((unsigned long long)mask) - 1;
+        uint32_t base = 0;
+        if ((int)lane == leader) base = atomicAdd(&c.count, (uint32_t)__popcll(mask));
+        base = (uint32_t)__shfl((int)base, leader, 64);
+        if (push) c.buf[base + (uint32_t)__popcll(mask & ((1ull << lane) - 1ull))] = comp;
+    }
+    // settle when the array could not take another round -- or as soon as k composites are there and no bound yet:
+    // from then on only offers that beat the k-th best are appended
+    if (__syncthreads_or(c.count + PQ_THREADS > PQ_BUF || (c.have < k && c.count >= k))) pq_collect_settle(c, k);
 }
 
 // (3) the nprobe best lists of each query: best first, ties to the smaller list number.
@@ -211,19 +243,21 @@ __global__ __launch_bounds__(PQ_THREADS) void pq_lut_kernel(const uint8_t *__res
                                                             uint32_t m, uint32_t dsub, uint32_t metric,
                                                             const float *__restrict__ cb, float *__restrict__ lut)
 {
+    __shared__ float qv[TRI_PQ_DSUB_MAX * 128];              // the query's dim <= 32 * 124 values
     const uint32_t q = blockIdx.x;
     const uint8_t *row = qrows + (size_t)q * row_bytes;
+    for (uint32_t i = threadIdx.x; i < m * dsub; i += PQ_THREADS) qv[i] = pq_elem(row, i, dtype);
+    __syncthreads();
     for (uint32_t t = threadIdx.x; t < m * TRI_PQ_KSUB; t += PQ_THREADS) {
-        const uint32_t mm = t / TRI_PQ_KSUB;
-        const float *entry = cb + (size_t)t * dsub;
+        const uint32_t mm = t / TRI_PQ_KSUB, c = t % TRI_PQ_KSUB;
         float acc = 0.f;
         for (uint32_t e = 0; e < dsub; ++e) {
-            const float x = pq_elem(row, mm * dsub + e, dtype);
+            const float x = qv[mm * dsub + e], y = cb[pq_cb_at(mm, c, e, dsub)];
             if (metric == 0u) {
-                const float d = x - entry[e];
+                const float d = x - y;
                 acc = __builtin_fmaf(d, d, acc);
             } else {
-                acc = __builtin_fmaf(-x, entry[e], acc);
+                acc = __builtin_fmaf(-x, y, acc);
             }
         }
         lut[(size_t)q * m * TRI_PQ_KSUB + t] = acc;
@@ -240,35 +274,69 @@ __global__ __launch_bounds__(PQ_THREADS) void pq_scan_kernel(const float *__rest
 {
     extern __shared__ float lut_lds[];
     __shared__ PqCollector col;
+    __shared__ uint32_t first[TRI_PQ_NPROBE_MAX], start[TRI_PQ_NPROBE_MAX + 1];   // per probed list: first stored position; running sum of lengths
     const uint32_t q = blockIdx.x;
-    for (uint32_t t = threadIdx.x; t < m * TRI_PQ_KSUB; t += PQ_THREADS) lut_lds[t] = lut[(size_t)q * m * TRI_PQ_KSUB + t];
+    {
+        const float4 *src = (const float4 *)(lut + (size_t)q * m * TRI_PQ_KSUB);
+#pragma unroll 4
+        for (uint32_t t = threadIdx.x; t < m * (TRI_PQ_KSUB / 4); t += PQ_THREADS) ((float4 *)lut_lds)[t] = src[t];
+    }
+    if (threadIdx.x == 0) {
+        uint32_t run = 0;
+        for (uint32_t p = 0; p < nprobe; ++p) {
+            const uint32_t l = probes[(size_t)q * nprobe + p];
+            first[p] = l == 0xFFFFFFFFu ? 0u : list_off[l];
+            start[p] = run;
+            run += l == 0xFFFFFFFFu ? 0u : list_off[l + 1] - list_off[l];
+        }
+        start[nprobe] = run;
+    }
     pq_collect_init(col);
-    const uint32_t words = m / 4;
-    for (uint32_t p = 0; p < nprobe; ++p) {
-        const uint32_t l = probes[(size_t)q * nprobe + p];
-        if (l == 0xFFFFFFFFu) continue;                                      // (uniform)
-        const uint32_t v0 = list_off[l], v1 = list_off[l + 1];
-        for (uint32_t vb = v0; vb < v1; vb += PQ_THREADS) {
-            const uint32_t v = vb + threadIdx.x;
-            const bool valid = v < v1;
-            float sum = 0.f;
-            if (valid) {
-                const uint32_t *code = (const uint32_t *)(codes + (size_t)v * m);
-                for (uint32_t w = 0; w < words; ++w) {
-                    const uint32_t c4 = code[w];
-                    const float *t = lut_lds + (size_t)w * 4 * TRI_PQ_KSUB;
-                    sum += t[c4 & 0xFFu];
-                    sum += t[TRI_PQ_KSUB + ((c4 >> 8) & 0xFFu)];
-                    sum += t[2 * TRI_PQ_KSUB + ((c4 >> 16) & 0xFFu)];
-                    sum += t[3 * TRI_PQ_KSUB + (c4 >> 24)];
+    // the vectors of all probed lists as ONE sequence (short lists would otherwise leave most of a round's threads
+    // idle): thread t of a round takes element r0 + t and finds its list by bisection in the running sums
+    const uint32_t groups = pq_mpad(m) / 16, total = start[nprobe];
+    for (uint32_t r0 = 0; r0 < total; r0 += PQ_THREADS) {
+        const uint32_t e = r0 + threadIdx.x;
+        const bool valid = e < total;
+        uint32_t v = 0;
+        if (valid) {
+            uint32_t lo = 0, hi = nprobe;                                  // start[lo] <= e < start[hi]
+            while (hi - lo > 1) {
+                const uint32_t mid = (lo + hi) / 2;
+                if (start[mid] <= e) lo = mid; else hi = mid;
+            }
+            v = first[lo] + (e - start[lo]);
+        }
+        float sum = 0.f;
+        if (valid) {
+            const uint4 *code = (const uint4 *)(codes + pq_code_at(v, 0, m));
+            uint4 cw[PQ_GROUPS_MAX];
+#pragma unroll
+            for (uint32_t g = 0; g < PQ_GROUPS_MAX; ++g)
+                if (g < groups) cw[g] = code[g * 64];                          // (uniform; all loads before the first look-up)
+#pragma unroll
+            for (uint32_t g = 0; g < PQ_GROUPS_MAX; ++g) {
+                if (g < groups) {
+                    const uint32_t w4[4] = {cw[g].x, cw[g].y, cw[g].z, cw[g].w};
+#pragma unroll
+                    for (uint32_t w = 0; w < 4; ++w) {
+                        const uint32_t mm = g * 16 + w * 4;
+                        if (mm < m) {                                              // (uniform: m is a multiple of 4)
+                            const float *t = lut_lds + (size_t)mm * TRI_PQ_KSUB;
+                            sum += t[w4[w] & 0xFFu];
+                            sum += t[TRI_PQ_KSUB + ((w4[w] >> 8) & 0xFFu)];
+                            sum += t[2 * TRI_PQ_KSUB + ((w4[w] >> 16) & 0xFFu)];
+                            sum += t[3 * TRI_PQ_KSUB + (w4[w] >> 24)];
+                        }
+                    }
                 }
             }
-            const uint32_t key = tri_score_key(sum, 0u);
-            // (the id is fetched only for a vector whose key alone does not rule it out)
-            const bool maybe = valid && ((uint64_t)key << 32) <= col.bound;
-            const uint64_t comp = maybe ? ((uint64_t)key << 32) | ids[v] : ~0ull;
-            pq_collect_round(col, k, maybe, comp);
         }
+        const uint32_t key = tri_score_key(sum, 0u);
+        // (the id is fetched only for a vector whose key alone does not rule it out)
+        const bool maybe = valid && ((uint64_t)key << 32) <= col.bound;
+        const uint64_t comp = maybe ? ((uint64_t)key << 32) | ids[v] : ~0ull;
+        pq_collect_round(col, k, maybe, comp);
     }
     pq_collect_settle(col, k);
     const uint32_t n = col.have;
@@ -288,8 +356,8 @@ struct tri_pq {
     TriIndexView view{};
     pq_params p{};
     uint32_t dsub = 0;
-    float *cb = nullptr;        // [m][256][dsub]
-    uint8_t *codes = nullptr;   // [n][m], list-major
+    float *cb = nullptr;        // [m][dsub][256] (pq_cb_at)
+    uint8_t *codes = nullptr;   // codes of the stored positions, in transposed blocks of 64 (pq_code_at)
 };
 
 namespace {
@@ -319,7 +387,7 @@ extern "C" int pq_build_bytes(const tri_index *index, const pq_params *p, size_t
     uint32_t dsub = 0;
     const int rc = pq_check(v, p, &dsub);
     if (rc) return rc;
-    *dev_bytes = up256((size_t)p->m * TRI_PQ_KSUB * dsub * 4) + up256((size_t)v.n * p->m);
+    *dev_bytes = up256((size_t)p->m * TRI_PQ_KSUB * dsub * 4) + up256((size_t)(v.n + 63) / 64 * 64 * pq_mpad(p->m));
     *tmp_bytes = up256((size_t)p->m * TRI_PQ_KSUB * dsub * 4) + up256((size_t)p->m * TRI_PQ_KSUB * 4);
     return TRI_OK;
 }
@@ -356,7 +424,11 @@ extern "C" int pq_build(const tri_index *index, const pq_params *p, const float 
     PQ_TRY_B(hipStreamSynchronize(s));
     const uint32_t lds = TRI_PQ_KSUB * dsub * 4;
     if (codebooks) {
-        PQ_TRY_B(hipMemcpyAsync(Q->cb, codebooks, cb_bytes, hipMemcpyHostToDevice, s));
+        std::vector<float> t((size_t)m * TRI_PQ_KSUB * dsub);
+        for (uint32_t mm = 0; mm < m; ++mm)
+            for (uint32_t c = 0; c < TRI_PQ_KSUB; ++c)
+                for (uint32_t e = 0; e < dsub; ++e) t[pq_cb_at(mm, c, e, dsub)] = codebooks[((size_t)mm * TRI_PQ_KSUB + c) * dsub + e];
+        PQ_TRY_B(hipMemcpy(Q->cb, t.data(), cb_bytes, hipMemcpyHostToDevice));
     } else {
         float *sums = (float *)tmp_dev;
         uint32_t *counts = (uint32_t *)((uint8_t *)tmp_dev + up256(cb_bytes));
@@ -402,8 +474,21 @@ extern "C" int pq_export(const tri_pq *pq, float *codebooks, uint8_t *codes)
     if (!pq) return tri_fail(TRI_EINVAL, "pq is NULL");
     PQ_TRY(hipSetDevice(pq->view.device));
     PQ_TRY(hipStreamSynchronize(pq->view.stream));
-    if (codebooks) PQ_TRY(hipMemcpy(codebooks, pq->cb, (size_t)pq->p.m * TRI_PQ_KSUB * pq->dsub * 4, hipMemcpyDeviceToHost));
-    if (codes) PQ_TRY(hipMemcpy(codes, pq->codes, (size_t)pq->view.n * pq->p.m, hipMemcpyDeviceToHost));
+    if (codebooks) {
+        const uint32_t m = pq->p.m, dsub = pq->dsub;
+        std::vector<float> raw((size_t)m * TRI_PQ_KSUB * dsub);
+        PQ_TRY(hipMemcpy(raw.data(), pq->cb, raw.size() * 4, hipMemcpyDeviceToHost));
+        for (uint32_t mm = 0; mm < m; ++mm)
+            for (uint32_t c = 0; c < TRI_PQ_KSUB; ++c)
+                for (uint32_t e = 0; e < dsub; ++e) codebooks[((size_t)mm * TRI_PQ_KSUB + c) * dsub + e] = raw[pq_cb_at(mm, c, e, dsub)];
+    }
+    if (codes) {
+        const uint32_t m = pq->p.m;
+        std::vector<uint8_t> raw((size_t)(pq->view.n + 63) / 64 * 64 * pq_mpad(m));
+        PQ_TRY(hipMemcpy(raw.data(), pq->codes, raw.size(), hipMemcpyDeviceToHost));
+        for (uint64_t v = 0; v < pq->view.n; ++v)
+            for (uint32_t mm = 0; mm < m; ++mm) codes[v * m + mm] = raw[pq_code_at(v, mm, m)];
+    }
     return TRI_OK;
 }
 
