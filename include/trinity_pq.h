@@ -69,12 +69,15 @@ int pq_search_bytes(const tri_pq *pq, uint32_t nq, size_t *ws_bytes /*[host] out
 
 /* Score a batch: for each of the nq query rows (the index's storage type, dim values, pitch_bytes apart, [device])
  * the nprobe best lists by `metric` against the centroids, every code of those lists, the k best by (score, id).
+ * k_adc = 0: the scores returned are the table sums.  k_adc >= k: re-ranking -- the k_adc best by table sums are
+ * scored again exactly against the index's stored vectors (squared L2 as the sum of squared differences, or the
+ * inner product, fp32) and the k best of those by (exact score, id) are returned with their exact scores.
  * Outputs [device]: ids_out [nq][k] (0xFFFFFFFF past n_out), dist_out [nq][k] (+inf / -inf past n_out),
- * n_out [nq], probes_out [nq][nprobe] or NULL (the probed lists, best first).  1 <= k <= TRI_PQ_KMAX,
+ * n_out [nq], probes_out [nq][nprobe] or NULL (the probed lists, best first).  1 <= k <= k_adc <= TRI_PQ_KMAX,
  * 1 <= nprobe <= min(nlist, TRI_PQ_NPROBE_MAX).  Asynchronous on the stream of the index's pool: outputs and ws
  * are in use until that stream has passed the call (pq_sync waits for it). */
 int pq_search_batch(tri_pq *pq, const void *queries /*[device]*/, size_t pitch_bytes, uint32_t nq, uint32_t k,
-                    uint32_t nprobe, uint32_t metric, void *ws /*[device]*/, size_t ws_bytes,
+                    uint32_t k_adc, uint32_t nprobe, uint32_t metric, void *ws /*[device]*/, size_t ws_bytes,
                     uint32_t *ids_out /*[device]*/, float *dist_out /*[device]*/, uint32_t *n_out /*[device]*/,
                     uint32_t *probes_out /*[device] or NULL*/);
 

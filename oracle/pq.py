@@ -110,3 +110,24 @@ def search(index: "oracle.Index", codes_listmajor: np.ndarray, codebooks: np.nda
     if all_candidates:
         return probe, out_ids, out_dist, n, ids[order], sc[order]
     return probe, out_ids, out_dist, n
+
+
+def search_reranked(index: "oracle.Index", codes_listmajor: np.ndarray, codebooks: np.ndarray, q: np.ndarray, k: int, k_adc: int,
+                    nprobe: int, metric: int, probe: np.ndarray = None):
+    """Two stages, as a deployment runs them: the k_adc best by reconstruction score (above), then those are scored
+    exactly against the stored vectors themselves (fp64) and the k best by (exact score, id) are the answer.
+    Returns (probe, ids[k], dist[k], n_out, stage1_ids, stage1_scores) -- the last two for every candidate, in stage-1
+    order, so that a checker can tell what was clearly in, clearly out, or at the boundary of the short list."""
+    probe, _, _, _, cand_ids, cand_sc = search(index, codes_listmajor, codebooks, q, k_adc, nprobe, metric, probe=probe,
+                                               all_candidates=True)
+    short = cand_ids[:k_adc]
+    x = index.base[short].astype(np.float64)
+    qq = np.asarray(q, dtype=np.float64)
+    exact = ((x - qq[None, :]) ** 2).sum(axis=1) if metric == METRIC_L2 else (x * qq[None, :]).sum(axis=1)
+    order = np.lexsort((short, exact if metric == METRIC_L2 else -exact))
+    n = min(k, order.shape[0])
+    out_ids = np.full(k, -1, dtype=np.int64)
+    out_dist = np.full(k, np.inf if metric == METRIC_L2 else -np.inf, dtype=np.float64)
+    out_ids[:n] = short[order[:n]]
+    out_dist[:n] = exact[order[:n]]
+    return probe, out_ids, out_dist, n, cand_ids, cand_sc

@@ -269,6 +269,9 @@ __global__ __launch_bounds__(PQ_THREADS) void pq_scan_kernel(const float *__rest
                                                              const uint32_t *__restrict__ probes, uint32_t nprobe,
                                                              const uint32_t *__restrict__ list_off, const uint32_t *__restrict__ ids,
                                                              const uint8_t *__restrict__ codes, uint32_t k, uint32_t metric,
+                                                             uint32_t k_adc, const uint8_t *__restrict__ qrows,
+                                                             const uint8_t *__restrict__ vecs, const uint32_t *__restrict__ inv,
+                                                             uint32_t row_bytes, uint32_t dtype,
                                                              uint32_t *__restrict__ ids_out, float *__restrict__ dist_out,
                                                              uint32_t *__restrict__ n_out)
 {
@@ -295,6 +298,7 @@ __global__ __launch_bounds__(PQ_THREADS) void pq_scan_kernel(const float *__rest
     // the vectors of all probed lists as ONE sequence (short lists would otherwise leave most of a round's threads
     // idle): thread t of a round takes element r0 + t and finds its list by bisection in the running sums
     const uint32_t groups = pq_mpad(m) / 16, total = start[nprobe];
+    const uint32_t ksel = k_adc ? k_adc : k;              // how many the table scores select
     for (uint32_t r0 = 0; r0 < total; r0 += PQ_THREADS) {
         const uint32_t e = r0 + threadIdx.x;
         const bool valid = e < total;
@@ -336,9 +340,43 @@ __global__ __launch_bounds__(PQ_THREADS) void pq_scan_kernel(const float *__rest
         // (the id is fetched only for a vector whose key alone does not rule it out)
         const bool maybe = valid && ((uint64_t)key << 32) <= col.bound;
         const uint64_t comp = maybe ? ((uint64_t)key << 32) | ids[v] : ~0ull;
-        pq_collect_round(col, k, maybe, comp);
+        pq_collect_round(col, ksel, maybe, comp);
     }
-    pq_collect_settle(col, k);
+    pq_collect_settle(col, ksel);
+    if (k_adc) {
+        // Re-ranking: the k_adc best by table scores are scored again exactly against the stored rows (found through
+        // the index's inverse id map) -- squared L2 in the difference form, or the inner product, fp32, one row per
+        // half-wavefront with a fixed reduction order -- and put in the order of those scores.
+        const uint32_t have = col.have, l32 = threadIdx.x & 31;
+        const uint8_t *qrow = qrows + (size_t)q * row_bytes;
+        for (uint32_t i = threadIdx.x >> 5; i < have; i += PQ_THREADS / 32) {
+            const uint32_t id = (uint32_t)(col.buf[i] & 0xFFFFFFFFu);
+            const uint8_t *x = vecs + (size_t)inv[id] * row_bytes;
+            float acc = 0.f;
+            for (uint32_t o = l32 * 16; o < row_bytes; o += 32 * 16) {
+                const uint4 xv = *(const uint4 *)(x + o), qv = *(const uint4 *)(qrow + o);
+                if (dtype == 1u) {
+                    const _Float16 *xe = (const _Float16 *)&xv, *qe = (const _Float16 *)&qv;
+#pragma unroll
+                    for (int j = 0; j < 8; ++j) {
+                        const float a = (float)xe[j], b = (float)qe[j];
+                        acc = metric == 0u ? __builtin_fmaf(a - b, a - b, acc) : __builtin_fmaf(-a, b, acc);
+                    }
+                } else {
+                    const float *xe = (const float *)&xv, *qe = (const float *)&qv;
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) acc = metric == 0u ? __builtin_fmaf(xe[j] - qe[j], xe[j] - qe[j], acc) : __builtin_fmaf(-xe[j], qe[j], acc);
+                }
+            }
+#pragma unroll
+            for (int dd = 16; dd > 0; dd >>= 1) acc += __shfl_xor(acc, dd, 32);
+            if (l32 == 0) col.buf[i] = ((uint64_t)tri_score_key(acc, 0u) << 32) | id;
+        }
+        __syncthreads();
+        pq_sort(col.buf, have);
+        if (threadIdx.x == 0) col.have = have < k ? have : k;
+        __syncthreads();
+    }
     const uint32_t n = col.have;
     for (uint32_t i = threadIdx.x; i < k; i += PQ_THREADS) {
         const bool real = i < n;
@@ -527,8 +565,8 @@ extern "C" int pq_search_bytes(const tri_pq *pq, uint32_t nq, size_t *ws_bytes)
     return TRI_OK;
 }
 
-extern "C" int pq_search_batch(tri_pq *pq, const void *queries, size_t pitch_bytes, uint32_t nq, uint32_t k, uint32_t nprobe,
-                               uint32_t metric, void *ws, size_t ws_bytes, uint32_t *ids_out, float *dist_out, uint32_t *n_out,
+extern "C" int pq_search_batch(tri_pq *pq, const void *queries, size_t pitch_bytes, uint32_t nq, uint32_t k, uint32_t k_adc,
+                               uint32_t nprobe, uint32_t metric, void *ws, size_t ws_bytes, uint32_t *ids_out, float *dist_out, uint32_t *n_out,
                                uint32_t *probes_out)
 {
     if (!pq || !queries || !ws || !ids_out || !dist_out || !n_out) return tri_fail(TRI_EINVAL, "NULL argument");
@@ -536,6 +574,7 @@ extern "C" int pq_search_batch(tri_pq *pq, const void *queries, size_t pitch_byt
     const uint32_t es = d.dtype == 1u ? 2u : 4u;
     if (nq == 0) return TRI_OK;
     if (k == 0 || k > TRI_PQ_KMAX) return tri_fail(TRI_EINVAL, "k must be 1..%u", TRI_PQ_KMAX);
+    if (k_adc && (k_adc < k || k_adc > TRI_PQ_KMAX)) return tri_fail(TRI_EINVAL, "k_adc must be 0 or k..%u", TRI_PQ_KMAX);
     if (nprobe == 0 || nprobe > TRI_PQ_NPROBE_MAX || nprobe > d.nlist) return tri_fail(TRI_EINVAL, "nprobe must be 1..min(nlist, %u)", TRI_PQ_NPROBE_MAX);
     if (metric != TRI_L2 && metric != TRI_IP) return tri_fail(TRI_EINVAL, "metric must be TRI_L2 or TRI_IP");
     if (pitch_bytes < (size_t)d.dim * es) return tri_fail(TRI_EINVAL, "pitch_bytes %zu is shorter than a query row (%u bytes)", pitch_bytes, d.dim * es);
@@ -562,7 +601,7 @@ extern "C" int pq_search_batch(tri_pq *pq, const void *queries, size_t pitch_byt
     hipLaunchKernelGGL(pq_lut_kernel, dim3(nq), dim3(PQ_THREADS), 0, s, w.qrows, d.row_bytes, d.dtype, m, pq->dsub, metric, pq->cb, w.lut);
     PQ_TRY(hipGetLastError());
     hipLaunchKernelGGL(pq_scan_kernel, dim3(nq), dim3(PQ_THREADS), lut_bytes, s, w.lut, m, probes, nprobe, d.list_off, d.ids, pq->codes,
-                       k, metric, ids_out, dist_out, n_out);
+                       k, metric, k_adc, w.qrows, (const uint8_t *)d.vecs, d.inv, d.row_bytes, d.dtype, ids_out, dist_out, n_out);
     PQ_TRY(hipGetLastError());
     return TRI_OK;
 }

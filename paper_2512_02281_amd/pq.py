@@ -29,7 +29,7 @@ def _bind():
     _lib.pq_destroy.argtypes = [vp]
     _lib.pq_export.argtypes = [vp, vp, vp]
     _lib.pq_search_bytes.argtypes = [vp, u32, P(sz)]
-    _lib.pq_search_batch.argtypes = [vp, vp, sz, u32, u32, u32, u32, vp, sz, vp, vp, vp, vp]
+    _lib.pq_search_batch.argtypes = [vp, vp, sz, u32, u32, u32, u32, u32, vp, sz, vp, vp, vp, vp]
     _lib.pq_sync.argtypes = [vp]
     for name in PQ_EXPORTS:
         getattr(_lib, name).restype = ctypes.c_int
@@ -77,9 +77,10 @@ class PQ:
         _check(_lib.pq_search_bytes(ctypes.c_void_p(self.handle), nq, ctypes.byref(ws)), "pq_search_bytes")
         return self.pool._device_bytes(ws.value), ws.value
 
-    def search(self, queries, k: int, nprobe: int, metric: int, ws=None, keep_probes: bool = True, out=None):
+    def search(self, queries, k: int, nprobe: int, metric: int, ws=None, keep_probes: bool = True, out=None, k_adc: int = 0):
         """queries: torch cuda tensor [nq, dim] of the index's storage type.  Returns torch tensors (ids int32 as
-        uint32 bits, dist, n_out[, probes]) on the device; asynchronous on the pool's stream (sync() waits)."""
+        uint32 bits, dist, n_out[, probes]) on the device; asynchronous on the pool's stream (sync() waits).
+        k_adc >= k: the k_adc best by table sums are re-ranked by their exact scores against the stored vectors."""
         import torch
         nq = int(queries.shape[0])
         if ws is None:
@@ -94,7 +95,7 @@ class PQ:
             else:
                 ids, dist, n_out, probes = out
         _check(_lib.pq_search_batch(ctypes.c_void_p(self.handle), ctypes.c_void_p(queries.data_ptr()),
-                                    int(queries.stride(0)) * queries.element_size(), nq, k, nprobe, metric,
+                                    int(queries.stride(0)) * queries.element_size(), nq, k, k_adc, nprobe, metric,
                                     ctypes.c_void_p(_aligned(ws_t)), ws_bytes, ctypes.c_void_p(ids.data_ptr()),
                                     ctypes.c_void_p(dist.data_ptr()), ctypes.c_void_p(n_out.data_ptr()),
                                     ctypes.c_void_p(probes.data_ptr()) if probes is not None else None), "pq_search_batch")

@@ -183,3 +183,62 @@ def test_edge_cases_and_argument_errors():
             with pytest.raises(tri.TriError) as ei:
                 pq.search(qt, 5, 2, 0, ws=(ws_t, ws_bytes - 256))
             assert ei.value.status == tri.TRI_ENOMEM
+
+
+@pytest.mark.parametrize("dtype,d,m", [("f16", 768, 96), ("f32", 128, 16)])
+def test_reranked_search_against_the_two_stage_oracle(dtype, d, m):
+    """k_adc > 0: the short list chosen by table sums is re-ranked by exact scores against the stored rows.  Where
+    the short list ends, table sums within rounding of each other may be cut either way, so the check is the
+    tie-aware one of both stages: every returned id belongs to a short list the oracle allows (its table score is not
+    worse than the oracle's k_adc-th beyond the tolerance), carries its exact score, the order is by exact score, and
+    no candidate that is surely in the short list and surely better than the returned k-th is missing."""
+    tri = harness.lib()
+    from paper_2512_02281_amd import pq as tpq
+    n, nlist = 16_000, 24
+    rng, base, pool, idx, oidx, torch = _setup(tri, dtype, n, d, nlist, seed=700 + d)
+    tol = checker.tolerance_for(oidx.dtype)
+    with pool, tpq.PQ(pool, idx, m, train_iters=4, train_rows=4000, seed=5) as pq:
+        cb, codes = pq.export(n, d)
+        nq = 32
+        queries = np.ascontiguousarray((base[rng.choice(n, nq)].astype(np.float64) + rng.normal(0, 0.3, size=(nq, d))).astype(base.dtype))
+        qt = torch.from_numpy(queries).cuda()
+        for k, k_adc, nprobe, metric in [(10, 100, 6, 0), (10, 256, 8, 1), (5, 5, 3, 1), (64, 200, nlist, 0)]:
+            ids, dist, n_out, probes = _to_host(*pq.search(qt, k, nprobe, metric, k_adc=k_adc))
+            pq.sync()
+            changed = 0
+            for i in range(nq):
+                q = queries[i]
+                coarse = oracle.coarse_scores(oidx, q, metric)
+                want_probe = oracle.probe_set(coarse, nprobe, metric)
+                use = want_probe if set(probes[i].tolist()) == set(want_probe.tolist()) else probes[i]
+                _, oids, odist, on, cand_ids, cand_sc = opq.search_reranked(oidx, codes, cb, q, k, k_adc, nprobe, metric, probe=use)
+                sign = 1.0 if metric == 0 else -1.0
+                assert n_out[i] == on
+                got = ids[i, :on]
+                assert len(set(got.tolist())) == on
+                # stage 1: what may be, and what must be, in the short list
+                if cand_ids.shape[0] > k_adc:
+                    tau1 = float(cand_sc[k_adc - 1])
+                    qn = float(np.sqrt((q.astype(np.float64) ** 2).sum()))
+                    band1 = 2e-4 * abs(tau1) + checker.ABS_EPS * qn * qn * 4
+                    allowed = set(cand_ids[sign * (cand_sc - tau1) <= band1].tolist())
+                    surely = cand_ids[sign * (tau1 - cand_sc) > band1]
+                else:
+                    allowed, surely = set(cand_ids.tolist()), cand_ids
+                assert set(got.tolist()) <= allowed, f"query {i}: an id outside every admissible short list"
+                # stage 2: exact scores, order, completeness
+                x = base[got].astype(np.float64)
+                exact = ((x - q.astype(np.float64)) ** 2).sum(axis=1) if metric == 0 else (x * q.astype(np.float64)).sum(axis=1)
+                scale = np.sqrt((q.astype(np.float64) ** 2).sum() * (x ** 2).sum(axis=1))
+                assert np.all(np.abs(dist[i, :on] - exact) <= checker.score_allowance(metric, tol, exact, scale)), f"query {i}: score is not the exact one"
+                assert np.all(sign * np.diff(dist[i, :on].astype(np.float64)) >= 0)
+                if on == k and surely.shape[0]:
+                    xs = base[surely].astype(np.float64)
+                    es = ((xs - q.astype(np.float64)) ** 2).sum(axis=1) if metric == 0 else (xs * q.astype(np.float64)).sum(axis=1)
+                    kth = float(exact[-1])
+                    band2 = tol * abs(kth) + checker.ABS_EPS * float(scale.max())
+                    must = set(surely[sign * (kth - es) > band2].tolist())
+                    assert must <= set(got.tolist()), f"query {i}: a surely better candidate is missing"
+                changed += int(not np.array_equal(got, oids[:on]))
+            _say(f"pq reranked {dtype} d={d}: k={k} k_adc={k_adc} nprobe={nprobe} metric={metric}: {nq - changed} of {nq} queries exactly the oracle's ids")
+            assert changed <= nq // 4

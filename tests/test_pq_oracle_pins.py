@@ -191,3 +191,29 @@ def test_the_empty_cell_rule_is_pinned():
     got = opq.train(X, init, 1)
     assert np.allclose(got[0, 0], [1 / 3, 1 / 3]) and np.array_equal(got[0, 1], [5.0, 5.0])
     assert not np.array_equal(_train_empty_cell_to_zero(X, init, 1)[0, 1], [5.0, 5.0])
+
+
+def test_reranking_pins():
+    """The two-stage search: with a short list as long as the candidate set the second stage decides alone, so the
+    answer must be the IVF-Flat oracle's; with lossless codebooks both stages score alike, so it must be the
+    one-stage answer; and a short list of exactly k returns the one-stage ids, re-ordered by their exact scores."""
+    rng = np.random.default_rng(11)
+    M, ksub, w, n, nlist = 4, 16, 3, 500, 5
+    X = rng.normal(size=(n, M * w)).astype(np.float32)
+    cb = opq.train(X, X[rng.choice(n, ksub, replace=False)].reshape(ksub, M, w).transpose(1, 0, 2), 3)
+    from oracle import index as oindex
+    idx = oindex.build_index(X, X[rng.choice(n, nlist, replace=False)], 0, train_iters=2)
+    codes_lm = opq.encode(X[idx.list_ids], cb)
+    for metric in (0, 1):
+        for t in range(10):
+            q = rng.normal(size=M * w).astype(np.float32)
+            probe, ids, dist, n_out, _, _ = opq.search_reranked(idx, codes_lm, cb, q, 7, n, 3, metric)
+            fp, fids, fdist, fn = oracle.search(idx, q, 7, 3, metric)
+            assert np.array_equal(ids, fids) and np.allclose(dist[:n_out], fdist[:fn], rtol=1e-12, atol=1e-12)
+            _, ids1, _, n1 = opq.search(idx, codes_lm, cb, q, 7, 3, metric)
+            _, ids2, dist2, n2, _, _ = opq.search_reranked(idx, codes_lm, cb, q, 7, 7, 3, metric)
+            assert n1 == n2 and sorted(ids1.tolist()) == sorted(ids2.tolist())
+            exact = ((X[ids2[:n2]].astype(np.float64) - q.astype(np.float64)) ** 2).sum(axis=1) if metric == 0 else \
+                (X[ids2[:n2]].astype(np.float64) * q.astype(np.float64)).sum(axis=1)
+            assert np.allclose(dist2[:n2], exact, rtol=1e-12, atol=1e-12)
+            assert np.all(np.diff(dist2[:n2]) >= 0) if metric == 0 else np.all(np.diff(dist2[:n2]) <= 0)
