@@ -104,7 +104,9 @@ typedef struct {
 int graph_step(tri_gpool *pool, tri_graph_step_stats *stats /*[host] out or NULL*/);
 
 /* Results of n tickets, as search_poll_batch delivers them: row i = best first, padded with id -1 and
- * +inf / -inf; iters[i] (may be NULL) = extends the request ran; evals[i] (may be NULL) = distances it
+ * +inf / -inf; squared L2 is delivered in the difference form sum (x - q)^2 (fp32), recomputed for the k
+ * rows handed back and ordered by (that, id), so a stored copy of the query has distance exactly 0 (the
+ * search itself ranks by |x|^2 + |q|^2 - 2 x.q); iters[i] (may be NULL) = extends the request ran; evals[i] (may be NULL) = distances it
  * computed.  status[i] = TRI_OK (delivered, ticket consumed), TRI_EAGAIN or TRI_ENOENT.  Returns the
  * number delivered or a negative tri_status. */
 int graph_poll(tri_gpool *pool, const tri_ticket *t /*[host] n*/, uint32_t n, uint32_t stride,

@@ -234,6 +234,22 @@ __device__ __forceinline__ float gx_dot16(const uint4 &x, const uint4 &q, float 
     return acc;
 }
 
+// acc + sum of (x - q)^2 over one 16-byte piece, in fp32
+template <int DT>
+__device__ __forceinline__ float gx_diff16(const uint4 &x, const uint4 &q, float acc)
+{
+    if (DT == TRI_F16) {
+        const _Float16 *a = (const _Float16 *)&x, *b = (const _Float16 *)&q;
+#pragma unroll
+        for (int i = 0; i < 8; ++i) { const float d = (float)a[i] - (float)b[i]; acc = fmaf(d, d, acc); }
+    } else {
+        const float *a = (const float *)&x, *b = (const float *)&q;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) { const float d = a[i] - b[i]; acc = fmaf(d, d, acc); }
+    }
+    return acc;
+}
+
 extern __shared__ __attribute__((aligned(16))) uint8_t gx_q[];   // the slot's query row
 
 template <int DT, int NCH>
@@ -279,6 +295,10 @@ __device__ __forceinline__ void gx_distance_phase(const GxDev &D, uint32_t s, co
 //          topM: the first p non-expanded ones (in topM's order) become parents and are marked; thread t
 //          takes neighbour t % D of parent t / D through the visited filter; the survivors, compacted, are
 //          the slot's distance tasks of the next step.
+//  result: the first k entries of topM.  The search ranks squared L2 in the expanded form |x|^2 + |q|^2 - 2 x.q
+//          (one contraction per row); what is handed back is the difference form: the k rows of a finishing
+//          L2 request are read once more, scored as sum (x - q)^2 and put in the order of (that, id), so a
+//          stored copy of the query comes back with distance exactly zero.
 __device__ __forceinline__ uint32_t gx_count_below(const unsigned long long *a, uint32_t n, unsigned long long x)
 {
     uint32_t lo = 0, hi = n;                 // a ascending: number of entries < x
@@ -289,6 +309,7 @@ __device__ __forceinline__ uint32_t gx_count_below(const unsigned long long *a, 
     return lo;
 }
 
+template <int DT>
 __device__ __forceinline__ void gx_merge_extend_phase(const GxDev &D, uint32_t s, GxMeta *mp, const GxMeta &m,
                                                       const float *__restrict__ sdist, unsigned long long old_e,
                                                       uint32_t task_id, uint32_t *__restrict__ done,
@@ -364,7 +385,45 @@ __device__ __forceinline__ void gx_merge_extend_phase(const GxDev &D, uint32_t s
     if (finish) {
         uint32_t *rec = rec_base + (size_t)s * rec_words;
         uint32_t n_valid = 0;
-        if (tid < M) {
+        if (m.metric == TRI_L2) {
+            const uint32_t kk = m.k < M ? m.k : M;
+            float *d2 = (float *)nw;                               // (nw and snew were last read before the barrier above)
+            const uint32_t team = tid / GX_TEAM, c = tid % GX_TEAM, pieces = D.row_pitch / 16;
+            const uint4 *q = (const uint4 *)(D.slot_q + (size_t)s * D.row_pitch);
+            for (uint32_t i = team; i < kk; i += GX_THREADS / GX_TEAM) {
+                const unsigned long long e = out[i];
+                float acc = 0.f;
+                if (e != ~0ull) {
+                    const uint4 *row = (const uint4 *)(D.vecs + (size_t)((uint32_t)(e & 0xFFFFFFFFull) >> 1) * D.row_pitch);
+                    for (uint32_t j = c; j < pieces; j += GX_TEAM) acc = gx_diff16<DT>(row[j], q[j], acc);
+                }
+#pragma unroll
+                for (int d = GX_TEAM / 2; d > 0; d >>= 1) acc += __shfl_xor(acc, d, GX_TEAM);
+                if (c == 0) d2[i] = acc;
+            }
+            __syncthreads();
+            if (tid < M) {
+                const unsigned long long e = out[tid];
+                const bool ok = e != ~0ull && tid < kk;
+                uint32_t at = tid;                                 // (empty entries stand behind the valid ones)
+                if (ok) {
+                    const uint32_t id = (uint32_t)(e & 0xFFFFFFFFull) >> 1;
+                    const unsigned long long mine2 = ((unsigned long long)__float_as_uint(d2[tid]) << 32) | id;
+                    at = 0;
+                    for (uint32_t j = 0; j < kk; ++j) {
+                        const unsigned long long o = out[j];
+                        if (o == ~0ull) break;
+                        at += (((unsigned long long)__float_as_uint(d2[j]) << 32) | ((uint32_t)(o & 0xFFFFFFFFull) >> 1)) < mine2;
+                    }
+                    rec[4 + at] = id;
+                    rec[4 + M + at] = __float_as_uint(d2[tid]);
+                } else {
+                    rec[4 + at] = 0xFFFFFFFFu;
+                    rec[4 + M + at] = 0u;
+                }
+                n_valid = ok;
+            }
+        } else if (tid < M) {
             const unsigned long long e = out[tid];
             const bool ok = e != ~0ull && tid < m.k;
             rec[4 + tid] = ok ? (uint32_t)(e & 0xFFFFFFFFull) >> 1 : 0xFFFFFFFFu;
@@ -407,7 +466,7 @@ __global__ __launch_bounds__(GX_THREADS) void gx_step_kernel(GxDev D, uint32_t *
     const uint32_t task_id = threadIdx.x < m.n_tasks ? D.tasks[(size_t)s * D.T + threadIdx.x] : TRI_GRAPH_PAD;
     if (m.n_tasks) gx_distance_phase<DT, NCH>(D, s, m, sdist);
     __syncthreads();
-    gx_merge_extend_phase(D, s, mp, m, sdist, old_e, task_id, done, rec_base, rec_words);
+    gx_merge_extend_phase<DT>(D, s, mp, m, sdist, old_e, task_id, done, rec_base, rec_words);
 }
 
 // ================================================================================== host side

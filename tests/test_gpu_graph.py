@@ -139,6 +139,37 @@ def test_both_kinds_of_visited_set_are_exact(flag):
             _check_exact((ids, dist, n_out, it, ev), want2, k2)
 
 
+def test_squared_l2_comes_back_in_the_difference_form():
+    """Real-valued data, squared L2.  The search ranks by |x|^2 + |q|^2 - 2 x.q; what is handed back is
+    sum (x - q)^2 of the k rows, in fp32, ordered by (that, id): every distance within fp32 summation error of the
+    fp64 one (far tighter than the expanded form allows when q is close to x), ascending, and a query that is a
+    stored row gets that row first with distance exactly zero."""
+    import torch
+    tri, tg = _lib()
+    n, dim, D, M, p, iters, k = 20_000, 768, 32, 64, 4, 64, 10
+    for np_dt, dt in ((np.float16, tri.TRI_F16), (np.float32, tri.TRI_F32)):
+        Xt, _ = graph_inputs.make_points(n, dim, 12, np_dt, graph_inputs.SEED_POINTS, device="cuda")
+        Qf, _ = graph_inputs.make_points(48, dim, 12, np_dt, graph_inputs.SEED_QUERIES, device="cuda")
+        Gt = graph_inputs.make_graph(Xt, D, 8, graph_inputs.SEED_EDGES)
+        X = Xt.cpu().numpy()
+        stored = np.arange(48) * 397 % n
+        Q = np.concatenate([X[stored], Qf.cpu().numpy()])
+        seeds = graph_inputs.entry_points(n, 64)
+        with tg.GraphPool(Xt, Gt.to(dtype=torch.int32), seeds, dt, slots=64, topm=M, parents=p, max_iters=iters) as pool:
+            ids, dist, n_out, it, ev, steps = pool.run_all(Q, k, tri.TRI_L2)
+        found = 0
+        for i in range(Q.shape[0]):
+            assert int(n_out[i]) == k and len(set(ids[i].tolist())) == k
+            true_sc = gs.scores(X, ids[i], Q[i], gs.METRIC_L2)
+            assert np.all(np.abs(dist[i] - true_sc) <= 4e-6 * true_sc), f"query {i}: not the difference form of its id"
+            assert np.all(dist[i][:-1] <= dist[i][1:])
+            if i < 48 and stored[i] in ids[i]:
+                found += 1
+                assert int(ids[i][0]) == int(stored[i]) and dist[i][0] == 0.0, f"query {i}: its own row is not at distance 0"
+        _say(f"L2 difference form ({np.dtype(np_dt).name}): {found}/48 stored queries found their own row, each at distance exactly 0")
+        assert found >= 40
+
+
 def test_real_valued_data_same_trajectories_where_no_decision_is_a_near_tie():
     """Real-valued fp16 data, inner product.  A search is a chain of decisions taken on scores; the oracle reports
     the smallest relative gap between neighbouring scores at any decision of a query (min_gap).  How far the
