@@ -291,17 +291,57 @@ hipError_t tri_build_cluster_means(hipStream_t s, int dtype, const void *rows, u
     return hipGetLastError();
 }
 
-// ------------------------------------------------------------------------------ inverse of the id array
-// inv[ids[p]] = p: where base row `id` is stored (ids is a permutation of 0..n-1).
-__global__ void invert_perm_kernel(const uint32_t *__restrict__ ids, uint64_t n, uint32_t *__restrict__ inv)
+// ------------------------------------------------------------------------------ where every base row is stored
+// Storage slot of the vector at stored position p: list l (the one with list_off[l] <= p < list_off[l + 1]) starts at
+// block blk_off[l]; slot = 32 * blk_off[l] + (p - list_off[l]).
+__device__ __forceinline__ uint32_t build_slot_of(uint32_t p, const uint32_t *__restrict__ list_off,
+                                                  const uint32_t *__restrict__ blk_off, uint32_t nlist)
 {
-    const uint64_t p = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (p < n) inv[ids[p]] = (uint32_t)p;
+    uint32_t lo = 0, hi = nlist;                 // last l with list_off[l] <= p (empty lists share their start: take the last)
+    while (hi - lo > 1) {
+        const uint32_t mid = (lo + hi) >> 1;
+        if (list_off[mid] <= p) lo = mid; else hi = mid;
+    }
+    return blk_off[lo] * 32u + (p - list_off[lo]);
 }
 
-hipError_t tri_build_invert_perm(hipStream_t s, const uint32_t *ids, uint64_t n, uint32_t *inv)
+// inv[ids[p]] = slot of p (ids is a permutation of 0..n-1).
+__global__ void slot_map_kernel(const uint32_t *__restrict__ ids, const uint32_t *__restrict__ list_off,
+                                const uint32_t *__restrict__ blk_off, uint32_t nlist, uint64_t n, uint32_t *__restrict__ inv)
+{
+    const uint64_t p = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (p < n) inv[ids[p]] = build_slot_of((uint32_t)p, list_off, blk_off, nlist);
+}
+
+hipError_t tri_build_slot_map(hipStream_t s, const uint32_t *ids, const uint32_t *list_off, const uint32_t *blk_off,
+                              uint32_t nlist, uint64_t n, uint32_t *inv)
 {
     if (n == 0) return hipSuccess;
-    hipLaunchKernelGGL(invert_perm_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, ids, n, inv);
+    hipLaunchKernelGGL(slot_map_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, ids, list_off, blk_off, nlist, n, inv);
+    return hipGetLastError();
+}
+
+// Rows p0 .. p0 + nrows - 1 (stored positions; row-major, pitch row_bytes, in `rows`) into their storage slots: one
+// thread per 16-byte piece, consecutive threads take the same piece of consecutive rows (contiguous in the block).
+__global__ void interleave_rows_kernel(const uint8_t *__restrict__ rows, uint32_t row_bytes, uint64_t p0, uint32_t nrows,
+                                       const uint32_t *__restrict__ ids, const uint32_t *__restrict__ inv,
+                                       uint8_t *__restrict__ vecs)
+{
+    const uint32_t pieces = row_bytes / 16;
+    const uint64_t t = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (t >= (uint64_t)nrows * pieces) return;
+    const uint32_t i = (uint32_t)(t % nrows), j = (uint32_t)(t / nrows);
+    const uint32_t slot = inv[ids[p0 + i]];
+    const uint4 v = *(const uint4 *)(rows + (size_t)i * row_bytes + j * 16);
+    *(uint4 *)(vecs + (size_t)(slot >> 5) * tri_block_stride(row_bytes) + (size_t)j * TRI_PIECE_PITCH + (slot & 31u) * 16u) = v;
+}
+
+hipError_t tri_build_interleave_rows(hipStream_t s, const void *rows, uint32_t row_bytes, uint64_t p0, uint32_t nrows,
+                                     const uint32_t *ids, const uint32_t *inv, void *vecs)
+{
+    if (nrows == 0) return hipSuccess;
+    const uint64_t total = (uint64_t)nrows * (row_bytes / 16);
+    hipLaunchKernelGGL(interleave_rows_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, s, (const uint8_t *)rows,
+                       row_bytes, p0, nrows, ids, inv, (uint8_t *)vecs);
     return hipGetLastError();
 }

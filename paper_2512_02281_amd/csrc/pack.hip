@@ -307,13 +307,15 @@ __device__ __forceinline__ void pack_tiles(uint32_t g, uint32_t total_lists, uin
     const uint32_t chunk_vecs = tri_chunk_vecs(len, min_chunk);
     const uint32_t nchunks = (len + chunk_vecs - 1) / chunk_vecs;
     const uint32_t voff = glist_voff[g];
+    // the list's blocks of 32 interleaved vectors (a chunk is a whole number of blocks)
+    const uint64_t list_addr = (uint64_t)(uintptr_t)ix.vecs + (uint64_t)ix.blk_off[g - ix.list_base] * tri_block_stride(ix.row_bytes);
     TriTile tl;
     tl.klass = tri_scan_class(ix.dtype, ix.row_bytes);
     tl.row_bytes = ix.row_bytes;
     uint32_t w = tile_base[g];
     for (uint32_t ch = 0; ch < nchunks; ++ch) {
         const uint32_t v0 = ch * chunk_vecs;
-        tl.vec_addr = (uint64_t)(uintptr_t)ix.vecs + (uint64_t)(voff + v0) * ix.row_bytes;
+        tl.vec_addr = list_addr + (uint64_t)(v0 / TRI_VB) * tri_block_stride(ix.row_bytes);
         tl.vnorm_addr = (uint64_t)(uintptr_t)(ix.vnorm + voff + v0);
         tl.vec_count = min(chunk_vecs, len - v0);
         tl.pitch = 0;
@@ -326,7 +328,7 @@ __device__ __forceinline__ void pack_tiles(uint32_t g, uint32_t total_lists, uin
             tiles[w++] = tl;
         }
     }
-    tl.vec_addr = (uint64_t)(uintptr_t)ix.vecs + (uint64_t)voff * ix.row_bytes;
+    tl.vec_addr = list_addr;
     tl.vnorm_addr = (uint64_t)(uintptr_t)(ix.vnorm + voff);
     tl.vec_count = min((uint32_t)TRI_SAMPLE_VECS, len);
     tl.pitch = TRI_SAMPLE_VECS;

@@ -53,14 +53,17 @@ __host__ __device__ __forceinline__ size_t pq_cb_at(uint32_t mm, uint32_t c, uin
     return ((size_t)mm * dsub + e) * TRI_PQ_KSUB + c;
 }
 
-__device__ __forceinline__ float pq_elem(const uint8_t *row, uint32_t i, uint32_t dtype)
+// Element i of the index's stored vector at stored position pos (the index keeps its vectors in blocks of 32,
+// interleaved by 16-byte pieces; a vector's storage slot is found through its id).
+__device__ __forceinline__ uint32_t pq_slot_of(const TriIndexDev &ix, uint64_t pos) { return ix.inv[ix.ids[pos]]; }
+__device__ __forceinline__ float pq_elem(const TriIndexDev &ix, uint32_t slot, uint32_t i)
 {
-    return dtype == 1u ? (float)((const _Float16 *)row)[i] : ((const float *)row)[i];
+    return ix.dtype == 1u ? (float)*(const _Float16 *)tri_slot_byte(ix, slot, i * 2u) : *(const float *)tri_slot_byte(ix, slot, i * 4u);
 }
 
 // ---------------------------------------------------------------------------------------- build
 // Stored position of training row r: every stride-th stored vector.
-__global__ void pq_init_kernel(const uint8_t *__restrict__ vecs, uint32_t row_bytes, uint32_t dtype, uint64_t n,
+__global__ void pq_init_kernel(const TriIndexDev ix, uint64_t n,
                                uint32_t m, uint32_t dsub, uint64_t seed, float *__restrict__ cb)
 {
     // entry c of every sub-space starts as the sub-vector of one stored vector: 256 positions spread over the
@@ -68,9 +71,10 @@ __global__ void pq_init_kernel(const uint8_t *__restrict__ vecs, uint32_t row_by
     const uint32_t c = blockIdx.x;
     const uint64_t step = n / TRI_PQ_KSUB;               // (n >= 256: at least 1)
     const uint64_t pos = ((uint64_t)c * step + seed % step) % n;
+    const uint32_t slot = pq_slot_of(ix, pos);
     for (uint32_t j = threadIdx.x; j < m * dsub; j += blockDim.x) {      // j over the dim values
         const uint32_t mm = j / dsub, e = j % dsub;
-        cb[pq_cb_at(mm, c, e, dsub)] = pq_elem(vecs + pos * row_bytes, j, dtype);
+        cb[pq_cb_at(mm, c, e, dsub)] = pq_elem(ix, slot, j);
     }
 }
 
@@ -99,8 +103,7 @@ __device__ __forceinline__ uint32_t pq_nearest(const float *cb_lds, const float 
 // TRAIN: rows are the training sample (every stride-th stored vector), the sub-vector is added to its cell's sum;
 // otherwise all stored vectors, the code is written.
 template <bool TRAIN>
-__global__ __launch_bounds__(PQ_THREADS) void pq_assign_kernel(const uint8_t *__restrict__ vecs, uint32_t row_bytes,
-                                                               uint32_t dtype, uint64_t rows, uint64_t stride, uint32_t m,
+__global__ __launch_bounds__(PQ_THREADS) void pq_assign_kernel(const TriIndexDev ix, uint64_t rows, uint64_t stride, uint32_t m,
                                                                uint32_t dsub, const float *__restrict__ cb,
                                                                float *__restrict__ sums, uint32_t *__restrict__ counts,
                                                                uint8_t *__restrict__ codes)
@@ -114,7 +117,8 @@ __global__ __launch_bounds__(PQ_THREADS) void pq_assign_kernel(const uint8_t *__
     if (r >= rows) return;
     const uint64_t pos = r * stride;
     float x[TRI_PQ_DSUB_MAX];
-    for (uint32_t e = 0; e < dsub; ++e) x[e] = pq_elem(vecs + pos * row_bytes, mm * dsub + e, dtype);
+    const uint32_t slot = pq_slot_of(ix, pos);
+    for (uint32_t e = 0; e < dsub; ++e) x[e] = pq_elem(ix, slot, mm * dsub + e);
     const uint32_t c = pq_nearest<TRI_PQ_DSUB_MAX>(cb_lds, x, dsub);
     if (TRAIN) {
         float *to = sums + ((size_t)mm * TRI_PQ_KSUB + c) * dsub;
@@ -246,7 +250,7 @@ __global__ __launch_bounds__(PQ_THREADS) void pq_lut_kernel(const uint8_t *__res
     __shared__ float qv[TRI_PQ_DSUB_MAX * 128];              // the query's dim <= 32 * 124 values
     const uint32_t q = blockIdx.x;
     const uint8_t *row = qrows + (size_t)q * row_bytes;
-    for (uint32_t i = threadIdx.x; i < m * dsub; i += PQ_THREADS) qv[i] = pq_elem(row, i, dtype);
+    for (uint32_t i = threadIdx.x; i < m * dsub; i += PQ_THREADS) qv[i] = dtype == 1u ? (float)((const _Float16 *)row)[i] : ((const float *)row)[i];
     __syncthreads();
     for (uint32_t t = threadIdx.x; t < m * TRI_PQ_KSUB; t += PQ_THREADS) {
         const uint32_t mm = t / TRI_PQ_KSUB, c = t % TRI_PQ_KSUB;
@@ -351,10 +355,11 @@ __global__ __launch_bounds__(PQ_THREADS) void pq_scan_kernel(const float *__rest
         const uint8_t *qrow = qrows + (size_t)q * row_bytes;
         for (uint32_t i = threadIdx.x >> 5; i < have; i += PQ_THREADS / 32) {
             const uint32_t id = (uint32_t)(col.buf[i] & 0xFFFFFFFFu);
-            const uint8_t *x = vecs + (size_t)inv[id] * row_bytes;
+            const uint32_t slot = inv[id];
+            const uint8_t *x = vecs + (size_t)(slot >> 5) * tri_block_stride(row_bytes) + (slot & 31u) * 16u;   // its pieces lie TRI_PIECE_PITCH apart
             float acc = 0.f;
             for (uint32_t o = l32 * 16; o < row_bytes; o += 32 * 16) {
-                const uint4 xv = *(const uint4 *)(x + o), qv = *(const uint4 *)(qrow + o);
+                const uint4 xv = *(const uint4 *)(x + (size_t)o * (TRI_PIECE_PITCH / 16)), qv = *(const uint4 *)(qrow + o);
                 if (dtype == 1u) {
                     const _Float16 *xe = (const _Float16 *)&xv, *qe = (const _Float16 *)&qv;
 #pragma unroll
@@ -473,14 +478,14 @@ extern "C" int pq_build(const tri_index *index, const pq_params *p, const float 
         uint64_t rows = p->train_rows ? p->train_rows : 65536;
         rows = std::min<uint64_t>(rows, v.n);
         const uint64_t stride = v.n / rows;
-        hipLaunchKernelGGL(pq_init_kernel, dim3(TRI_PQ_KSUB), dim3(1024), 0, s, (const uint8_t *)v.dev.vecs, v.dev.row_bytes,
-                           v.dev.dtype, v.n, m, dsub, p->seed, Q->cb);
+        hipLaunchKernelGGL(pq_init_kernel, dim3(TRI_PQ_KSUB), dim3(1024), 0, s, v.dev,
+                           v.n, m, dsub, p->seed, Q->cb);
         PQ_TRY_B(hipGetLastError());
         for (uint32_t it = 0; it < p->train_iters; ++it) {
             PQ_TRY_B(tri_launch_fill_u32(s, (uint32_t *)sums, 0u, cb_bytes / 4));
             PQ_TRY_B(tri_launch_fill_u32(s, counts, 0u, (size_t)m * TRI_PQ_KSUB));
             hipLaunchKernelGGL(pq_assign_kernel<true>, dim3((unsigned)((rows + PQ_THREADS - 1) / PQ_THREADS), m), dim3(PQ_THREADS), lds, s,
-                               (const uint8_t *)v.dev.vecs, v.dev.row_bytes, v.dev.dtype, rows, stride, m, dsub, Q->cb, sums, counts,
+                               v.dev, rows, stride, m, dsub, Q->cb, sums, counts,
                                (uint8_t *)nullptr);
             PQ_TRY_B(hipGetLastError());
             const uint32_t total = m * TRI_PQ_KSUB * dsub;
@@ -489,7 +494,7 @@ extern "C" int pq_build(const tri_index *index, const pq_params *p, const float 
         }
     }
     hipLaunchKernelGGL(pq_assign_kernel<false>, dim3((unsigned)((v.n + PQ_THREADS - 1) / PQ_THREADS), m), dim3(PQ_THREADS), lds, s,
-                       (const uint8_t *)v.dev.vecs, v.dev.row_bytes, v.dev.dtype, v.n, (uint64_t)1, m, dsub, Q->cb, (float *)nullptr,
+                       v.dev, v.n, (uint64_t)1, m, dsub, Q->cb, (float *)nullptr,
                        (uint32_t *)nullptr, Q->codes);
     PQ_TRY_B(hipGetLastError());
     PQ_TRY_B(hipStreamSynchronize(s));

@@ -39,10 +39,14 @@
 //    queries through LDS (row pitch = row bytes + 16: conflict-free 16-byte operand reads).
 //
 // Memory behaviour of both: each lane loads 16-byte pieces straight from the list into MFMA operand
-// registers; the four loads a wavefront issues for one 128-byte group cover one full 128-byte line
-// of each of its 32 vectors.  Loads go through buffer descriptors sized to the chunk, so rows past
-// the end of a list and prefetches past its last block return zeros without touching memory and
-// the stream needs no branches.  The issue order is pinned with scheduling barriers, which lets the
+// registers.  The index stores a list in blocks of 32 vectors interleaved by 16-byte pieces (piece j of the
+// block's vector i at j * 512 + i * 16), which is the order in which a wavefront's lanes want them: lane
+// (kg, r) holds piece 8g + 2c + kg of vector r for load (g, c), so every load instruction reads ONE CONTIGUOUS
+// KiB -- eight full 128-byte lines, 16 cache accesses per instruction instead of the 64 that 32 rows a row
+// length apart cost (the vector cache's tag pipeline was busy or stalled 98 % of the time with row-major lists).
+// Loads go through buffer descriptors sized to the chunk's blocks; a lane whose storage slot lies behind the
+// chunk's last vector, and prefetches past the last block, ask out of range and get zeros without touching
+// memory, so the stream needs no branches.  The issue order is pinned with scheduling barriers, which lets the
 // compiler count outstanding loads exactly and wait only for the oldest ones.  Dense scores (sample
 // launch) leave as complete 128-byte lines (32 consecutive vectors of one query per half-wavefront
 // store); filtered candidates leave in bursts (see scan_stage_block).
@@ -58,6 +62,13 @@ __device__ __forceinline__ uint4 scan_ld16(__amdgpu_buffer_rsrc_t rs, uint32_t o
 {
     const scan_u32x4 v = __builtin_amdgcn_raw_buffer_load_b128(rs, off, 0, 0);
     return make_uint4(v.x, v.y, v.z, v.w);
+}
+
+// Where lane (kg, r) starts in block b of a chunk of len vectors: its slot's 16 bytes of piece kg; out of range
+// (zeros, no read) when the slot lies behind the chunk's last vector.  (Offsets stay below 2^31: see the index build.)
+__device__ __forceinline__ uint32_t scan_lane_off(uint32_t b, uint32_t r, uint32_t kg, uint32_t len, uint32_t blk_bytes)
+{
+    return b * TRI_VB + r < len ? b * blk_bytes + kg * TRI_PIECE_PITCH + r * 16u : 0x80000000u;
 }
 
 // Scores of one 32-vector block.  The MFMA takes the query pieces as its first operand, so
@@ -190,21 +201,24 @@ __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(1, 1))) void
         if (tl.klass == my_class) {
             const uint32_t len = tl.vec_count;
             const uint32_t nblocks = (len + TRI_VB - 1) / TRI_VB;
-            const __amdgpu_buffer_rsrc_t vrs =
-                __builtin_amdgcn_make_buffer_rsrc((void *)tl.vec_addr, 0, len * row_bytes, SCAN_BUF_FLAGS);
-            // (sized to whole blocks: a 16-byte load never straddles its end; the norm array has a block of slack)
+            const __amdgpu_buffer_rsrc_t vrs =         // (whole blocks: that is how the chunk is stored)
+                __builtin_amdgcn_make_buffer_rsrc((void *)tl.vec_addr, 0, nblocks * blk_bytes, SCAN_BUF_FLAGS);
+            // (sized to whole blocks: the norm array has a block of slack)
             const __amdgpu_buffer_rsrc_t nrs =
                 __builtin_amdgcn_make_buffer_rsrc((void *)tl.vnorm_addr, 0, nblocks * TRI_VB * 4u, SCAN_BUF_FLAGS);
             // (main launch: the first TRI_SAMPLE_VECS vectors of a list were scored by the sample launch, and what
             // passed of them already heads the candidate regions; the scan of a list's first chunk starts behind them)
             const uint32_t b0 = FILTER && tl.vec_begin == 0 ? TRI_SAMPLE_VECS / TRI_VB : 0u;
             // the stream's first RG groups go out before anything else
-            uint32_t off = r * row_bytes + kg * 16 + b0 * blk_bytes;
+            // (lane l = (kg, r) holds pieces 8g + 2c + kg of vector r: its 16 bytes of load (g, c) lie at
+            // (8g + 2c + kg) * 512 + r * 16 of the block, so one load instruction reads one contiguous KiB; a lane
+            // whose slot lies behind the chunk's last vector asks out of range and gets zeros without a read)
+            uint32_t off = scan_lane_off(b0, r, kg, len, blk_bytes);
             uint4 buf[RG][4];
 #pragma unroll
             for (int g = 0; g < RG; ++g) {
 #pragma unroll
-                for (int c = 0; c < 4; ++c) buf[g][c] = scan_ld16(vrs, off + g * 128 + c * 32);
+                for (int c = 0; c < 4; ++c) buf[g][c] = scan_ld16(vrs, off + g * 4096 + c * 1024);
                 __builtin_amdgcn_sched_barrier(0);
             }
             // this lane's query (row l%32 of the first MFMA operand): its vector as operand pieces; a
@@ -256,7 +270,8 @@ __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(1, 1))) void
             const uint32_t pos_base = (uint32_t)tl.out_off;     // (main launch: stored position of the chunk's first vector)
             __builtin_amdgcn_sched_barrier(0);
 
-            for (uint32_t b = b0; b < nblocks; ++b, off += blk_bytes) {
+            for (uint32_t b = b0; b < nblocks; ++b) {
+                const uint32_t off_next = scan_lane_off(b + 1, r, kg, len, blk_bytes);
                 // |x|^2 of this lane's vector, issued before the prefetches below so that waiting
                 // for it never waits for them (vector-memory operations complete in order)
                 const float vn = __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(nrs, (b * TRI_VB + r) * 4u, 0, 0));
@@ -271,11 +286,12 @@ __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(1, 1))) void
                     for (int c = 0; c < 4; ++c)
                         tri_mma32<DT>(acc, make_uint4(qf[g][c].x, qf[g][c].y, qf[g][c].z, qf[g][c].w), buf[sl][c]);
                     __builtin_amdgcn_sched_barrier(0);
-                    const uint32_t nxt = g + RG < NG ? off + (g + RG) * 128 : off + blk_bytes + (g + RG - NG) * 128;
+                    const uint32_t nxt = g + RG < NG ? off + (g + RG) * 4096 : off_next + (g + RG - NG) * 4096;
 #pragma unroll
-                    for (int c = 0; c < 4; ++c) buf[sl][c] = scan_ld16(vrs, nxt + c * 32);
+                    for (int c = 0; c < 4; ++c) buf[sl][c] = scan_ld16(vrs, nxt + c * 1024);
                     __builtin_amdgcn_sched_barrier(0);
                 }
+                off = off_next;
                 if (!ahead) {
                     // The claim of the next tile has come back by now (it was issued before this tile's first
                     // loads, and loads return in order): its descriptor is fetched while the rest of this tile
@@ -396,9 +412,10 @@ __device__ __forceinline__ void scan_tile_pipelined(const TriTile &tl, const uin
     constexpr uint32_t row_bytes = NG * 128;
     const uint32_t len = tl.vec_count;
     const uint32_t nblocks = (len + TRI_VB - 1) / TRI_VB;
+    constexpr uint32_t blk_bytes = TRI_VB * row_bytes;
     const __amdgpu_buffer_rsrc_t vrs =
-        __builtin_amdgcn_make_buffer_rsrc((void *)tl.vec_addr, 0, len * row_bytes, SCAN_BUF_FLAGS);
-    const __amdgpu_buffer_rsrc_t nrs =      // whole blocks: a 16-byte load never straddles its end
+        __builtin_amdgcn_make_buffer_rsrc((void *)tl.vec_addr, 0, nblocks * blk_bytes, SCAN_BUF_FLAGS);
+    const __amdgpu_buffer_rsrc_t nrs =
         __builtin_amdgcn_make_buffer_rsrc((void *)tl.vnorm_addr, 0, nblocks * TRI_VB * 4u, SCAN_BUF_FLAGS);
     const uint8_t *qrow = qlds + r * pitch + kg * 16;
     float qn[16];
@@ -414,18 +431,19 @@ __device__ __forceinline__ void scan_tile_pipelined(const TriTile &tl, const uin
         (void *)(out_buf + (FILTER ? 0 : tl.out_off)), 0, FILTER ? 0u : ((tl.nq - 1) * tl.pitch + nblocks * TRI_VB) * 4u,
         SCAN_BUF_FLAGS);
     const uint32_t lane_off = 4 * kg * pitch_bytes + r * 4;
-    constexpr uint32_t bstride = (TRI_SCAN_THREADS / 64) * TRI_VB * row_bytes;   // to the wavefront's next block
+    constexpr uint32_t NWV = TRI_SCAN_THREADS / 64;                              // blocks from one of the wavefront's to its next
 
     const uint32_t b0 = FILTER && tl.vec_begin == 0 ? TRI_SAMPLE_VECS / TRI_VB : 0u;    // (the sample launch scored the list's first blocks)
-    uint32_t off = ((b0 + wave) * TRI_VB + r) * row_bytes + kg * 16;
+    uint32_t off = scan_lane_off(b0 + wave, r, kg, len, blk_bytes);
     uint4 buf[SCAN_RING][4];
 #pragma unroll
     for (int s = 0; s < SCAN_RING; ++s) {
 #pragma unroll
-        for (int c = 0; c < 4; ++c) buf[s][c] = scan_ld16(vrs, off + s * 128 + c * 32);
+        for (int c = 0; c < 4; ++c) buf[s][c] = scan_ld16(vrs, off + s * 4096 + c * 1024);
         __builtin_amdgcn_sched_barrier(0);
     }
-    for (uint32_t b = b0 + wave; b < nblocks; b += TRI_SCAN_THREADS / 64, off += bstride) {
+    for (uint32_t b = b0 + wave; b < nblocks; b += NWV) {
+        const uint32_t off_next = scan_lane_off(b + NWV, r, kg, len, blk_bytes);
         const float vn = __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(nrs, (b * TRI_VB + r) * 4u, 0, 0));
         __builtin_amdgcn_sched_barrier(0);
         tri_f32x16 acc;
@@ -440,12 +458,13 @@ __device__ __forceinline__ void scan_tile_pipelined(const TriTile &tl, const uin
                 tri_mma32<DT>(acc, q, buf[s][c]);
             }
             __builtin_amdgcn_sched_barrier(0);
-            const uint32_t nxt = g + SCAN_RING < NG ? off + (g + SCAN_RING) * 128
-                                                    : off + bstride + (g + SCAN_RING - NG) * 128;
+            const uint32_t nxt = g + SCAN_RING < NG ? off + (g + SCAN_RING) * 4096
+                                                    : off_next + (g + SCAN_RING - NG) * 4096;
 #pragma unroll
-            for (int c = 0; c < 4; ++c) buf[s][c] = scan_ld16(vrs, nxt + c * 32);
+            for (int c = 0; c < 4; ++c) buf[s][c] = scan_ld16(vrs, nxt + c * 1024);
             __builtin_amdgcn_sched_barrier(0);
         }
+        off = off_next;
         if constexpr (FILTER)
             scan_filter_block(acc, vn, qn, l2mask, sh, out, kg, tl.nq, b * TRI_VB + r < len, b * TRI_VB + r);
         else
@@ -466,9 +485,10 @@ __device__ __forceinline__ void scan_tile_generic(const TriTile &tl, const uint8
     const uint32_t ngroups = row_bytes / 128;
     const uint32_t len = tl.vec_count;
     const uint32_t nblocks = (len + TRI_VB - 1) / TRI_VB;
+    const uint32_t blk_bytes = tri_block_stride(row_bytes);
     const __amdgpu_buffer_rsrc_t vrs =
-        __builtin_amdgcn_make_buffer_rsrc((void *)tl.vec_addr, 0, len * row_bytes, SCAN_BUF_FLAGS);
-    const __amdgpu_buffer_rsrc_t nrs =      // whole blocks: a 16-byte load never straddles its end
+        __builtin_amdgcn_make_buffer_rsrc((void *)tl.vec_addr, 0, nblocks * blk_bytes, SCAN_BUF_FLAGS);
+    const __amdgpu_buffer_rsrc_t nrs =
         __builtin_amdgcn_make_buffer_rsrc((void *)tl.vnorm_addr, 0, nblocks * TRI_VB * 4u, SCAN_BUF_FLAGS);
     const uint8_t *qrow = qlds + r * pitch + kg * 16;
     float qn[16];
@@ -487,7 +507,7 @@ __device__ __forceinline__ void scan_tile_generic(const TriTile &tl, const uint8
 
     const uint32_t b0 = FILTER && tl.vec_begin == 0 ? TRI_SAMPLE_VECS / TRI_VB : 0u;    // (the sample launch scored the list's first blocks)
     for (uint32_t b = b0 + wave; b < nblocks; b += TRI_SCAN_THREADS / 64) {
-        const uint32_t off = (b * TRI_VB + r) * row_bytes + kg * 16;
+        const uint32_t off = scan_lane_off(b, r, kg, len, blk_bytes);
         const float vn = __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(nrs, (b * TRI_VB + r) * 4u, 0, 0));
         tri_f32x16 acc;
 #pragma unroll
@@ -498,7 +518,7 @@ __device__ __forceinline__ void scan_tile_generic(const TriTile &tl, const uint8
             for (int s = 0; s < SCAN_RING; ++s)
 #pragma unroll
                 for (int c = 0; c < 4; ++c)     // groups past the row end: offset forced out of range -> zeros
-                    buf[s][c] = scan_ld16(vrs, g0 + s < ngroups ? off + (g0 + s) * 128 + c * 32 : 0xFFFFFFF0u);
+                    buf[s][c] = scan_ld16(vrs, g0 + s < ngroups ? off + (g0 + s) * 4096 + c * 1024 : 0xFFFFFFF0u);
 #pragma unroll
             for (int s = 0; s < SCAN_RING; ++s) {
                 const uint32_t g = g0 + s < ngroups ? g0 + s : 0u;   // (zeros times any valid query piece)

@@ -172,25 +172,25 @@ __device__ __forceinline__ void sel_cache_segments(SelShared &sh, uint32_t nps, 
     __syncthreads();
 }
 
-// Scores of 32 stored vectors (v0 .. v0 + 31 of a list that starts at `list`) against the query, by one wavefront:
+// Scores of the 32 stored vectors of one block (at `block`: 32 vectors interleaved by 16-byte pieces, zeros behind
+// the list's last vector) against the query, by one wavefront:
 // the query's pieces as the first operand of every product (all 32 rows of that operand are the query), the
 // vectors' as the second, 128-byte group after group and 32-byte chunk after chunk -- the order in which the scan
 // kernels accumulate, so the sums come out bit for bit the same.  Lane l returns the score of vector v0 + l % 32.
 template <int DT>
-__device__ __forceinline__ float sel_rescan_block(const SelRescan &rs, const uint8_t *__restrict__ list, uint32_t v0, uint32_t len,
-                                                  uint32_t lane)
+__device__ __forceinline__ float sel_rescan_block(const SelRescan &rs, const uint8_t *__restrict__ block, uint32_t lane)
 {
     const uint32_t r = lane & 31, kg = lane >> 5;
     const uint32_t row_bytes = rs.ix->row_bytes;
-    const uint32_t v = v0 + r < len ? v0 + r : len - 1;                  // (rows past the end: any valid row, never used)
-    const uint8_t *x = list + (size_t)v * row_bytes + kg * 16;
+    const uint8_t *x = block + kg * TRI_PIECE_PITCH + r * 16;            // piece 8g + 2c + kg of vector r: + g * 4096 + c * 1024
     const uint8_t *q = rs.qrow + kg * 16;
     tri_f32x16 acc;
 #pragma unroll
     for (int i = 0; i < 16; ++i) acc[i] = 0.f;
     for (uint32_t g = 0; g < row_bytes; g += 128)
 #pragma unroll
-        for (int c = 0; c < 4; ++c) tri_mma32<DT>(acc, *(const uint4 *)(q + g + c * 32), *(const uint4 *)(x + g + c * 32));
+        for (int c = 0; c < 4; ++c)
+            tri_mma32<DT>(acc, *(const uint4 *)(q + g + c * 32), *(const uint4 *)(x + (size_t)g * 32 + c * 1024));
     return acc[0];
 }
 
@@ -206,11 +206,12 @@ __device__ __forceinline__ void sel_rescan_for_each(const SelRescan &rs, uint32_
     for (uint32_t it = 0; it < rs.take; ++it) {
         const uint32_t g = rs.item_glist[rs.item_base + it];
         const uint32_t len = rs.glist_len[g], voff = rs.glist_voff[g];
-        const uint8_t *list = (const uint8_t *)rs.ix->vecs + (size_t)voff * row_bytes;
+        const uint8_t *list = (const uint8_t *)rs.ix->vecs + (size_t)rs.ix->blk_off[g - rs.ix->list_base] * tri_block_stride(row_bytes);
         for (uint32_t v0 = 0; v0 < len; v0 += 32, ++gblock) {
             if (gblock % stride != 0 || (gblock / stride) % NW != wave) continue;
-            const float dot = rs.ix->dtype == 1u ? sel_rescan_block<TRI_DT_F16>(rs, list, v0, len, lane)
-                                                 : sel_rescan_block<TRI_DT_F32>(rs, list, v0, len, lane);
+            const uint8_t *block = list + (size_t)(v0 / 32u) * tri_block_stride(row_bytes);
+            const float dot = rs.ix->dtype == 1u ? sel_rescan_block<TRI_DT_F16>(rs, block, lane)
+                                                 : sel_rescan_block<TRI_DT_F32>(rs, block, lane);
             const uint32_t v = v0 + (lane & 31);
             const bool valid = lane < 32 && v < len;
             const float vn = rs.ix->vnorm[voff + (valid ? v : v0)];
@@ -1125,8 +1126,9 @@ hipError_t tri_launch_threshold(const TriLaunchCtx &c, const TriDevWs &ws, uint3
     return hipGetLastError();
 }
 
-// Squared L2 distance of a stored row to a query row in the difference form, sum of (x_i - q_i)^2, by the 32
-// lanes of a half-wavefront: lane l takes the 16-byte pieces l, l + 32, ... of both rows, the partial sums are
+// Squared L2 distance of a stored vector (x: its first 16-byte piece; the pieces lie TRI_PIECE_PITCH apart) to a
+// query row in the difference form, sum of (x_i - q_i)^2, by the 32
+// lanes of a half-wavefront: lane l takes the 16-byte pieces l, l + 32, ... of both, the partial sums are
 // combined by a butterfly (a fixed order, the same in every lane).  fp32 arithmetic; fp16 inputs widen exactly.
 template <typename T>
 __device__ __forceinline__ float sel_l2_diff_form(const uint8_t *__restrict__ x, const uint8_t *__restrict__ q, uint32_t row_bytes,
@@ -1135,7 +1137,7 @@ __device__ __forceinline__ float sel_l2_diff_form(const uint8_t *__restrict__ x,
     constexpr int PER = 16 / sizeof(T);
     float acc = 0.f;
     for (uint32_t o = l32 * 16; o < row_bytes; o += 32 * 16) {
-        const uint4 xv = *(const uint4 *)(x + o), qv = *(const uint4 *)(q + o);
+        const uint4 xv = *(const uint4 *)(x + (size_t)o * (TRI_PIECE_PITCH / 16)), qv = *(const uint4 *)(q + o);
         const T *xe = (const T *)&xv, *qe = (const T *)&qv;
 #pragma unroll
         for (int i = 0; i < PER; ++i) {
@@ -1380,7 +1382,7 @@ __device__ __forceinline__ bool merge_wave(const MergeArgs &A, const TriPlanEntr
         thr_wave_fence();
         for (uint32_t i = lane >> 5; i < n; i += 2) {
             const uint32_t id = (uint32_t)(L.b[i] & 0xFFFFFFFFu);
-            const uint8_t *x = (const uint8_t *)ix.vecs + (size_t)stored[i] * ix.row_bytes;
+            const uint8_t *x = tri_slot_ptr(ix, stored[i]);
             const float d2 = ix.dtype == 1u ? sel_l2_diff_form<_Float16>(x, qrow, ix.row_bytes, l32)
                                             : sel_l2_diff_form<float>(x, qrow, ix.row_bytes, l32);
             if (l32 == 0) L.a[i] = ((uint64_t)sel_key(d2, 0u) << 32) | id;
@@ -1433,7 +1435,7 @@ __device__ void merge_block(const MergeArgs &A, const TriPlanEntry &e, SelShared
         const uint32_t l32 = threadIdx.x & 31;
         for (uint32_t i = threadIdx.x >> 5; i < n; i += TRI_SEL_THREADS / 32) {
             const uint32_t id = (uint32_t)(best[i] & 0xFFFFFFFFu);
-            const uint8_t *x = (const uint8_t *)ix.vecs + (size_t)ix.inv[id] * ix.row_bytes;
+            const uint8_t *x = tri_slot_ptr(ix, ix.inv[id]);
             const float d2 = ix.dtype == 1u ? sel_l2_diff_form<_Float16>(x, qrow, ix.row_bytes, l32)
                                             : sel_l2_diff_form<float>(x, qrow, ix.row_bytes, l32);
             if (l32 == 0) fresh[i] = ((uint64_t)sel_key(d2, 0u) << 32) | id;

@@ -674,6 +674,9 @@ extern "C" int tri_pool_destroy(tri_pool *P)
 }
 
 // ================================================================================== index
+// Most blocks of 32 storage slots that n vectors in nlist lists can occupy (every list ends in a partly filled block).
+static size_t index_blocks_max(uint64_t n, uint32_t nlist) { return (size_t)((n + 31ull * nlist + 31ull) / 32ull); }
+
 extern "C" int ivf_build_bytes(const ivf_params *p, uint64_t n, size_t *dev_bytes)
 {
     if (!p || !dev_bytes) return tri_fail(TRI_EINVAL, "NULL argument");
@@ -684,11 +687,12 @@ extern "C" int ivf_build_bytes(const ivf_params *p, uint64_t n, size_t *dev_byte
     const uint32_t dpad = dpad_of(p->dim, p->dtype), rb = dpad * esize(p->dtype);
     if (rb > TRI_MAX_ROW_BYTES) return tri_fail(TRI_EINVAL, "padded row of %u bytes exceeds %u", rb, TRI_MAX_ROW_BYTES);
     size_t o = 0;
-    o += round_up_sz((size_t)n * rb, 256);                 // vectors
+    o += round_up_sz(index_blocks_max(n, p->nlist) * tri_block_stride(rb), 256);   // vectors: whole blocks of 32 per list
     o += round_up_sz(((size_t)n + TRI_VB) * 4, 256);       // |x|^2 (+ one block of slack for tail reads)
     o += round_up_sz((size_t)n * 4, 256);                  // ids
     o += round_up_sz((size_t)n * 4, 256);                  // stored position of every base row
     o += round_up_sz(((size_t)p->nlist + 1) * 4, 256);     // list offsets
+    o += round_up_sz(((size_t)p->nlist + 1) * 4, 256);     // first block of every list
     o += round_up_sz((size_t)p->nlist * rb, 256);          // centroids
     o += round_up_sz((size_t)p->nlist * 4, 256);           // |c|^2
     *dev_bytes = o;
@@ -824,11 +828,13 @@ extern "C" int ivf_build(tri_pool *P, const ivf_params *p, const void *base, uin
 
     // carve dev_mem
     uint8_t *m = (uint8_t *)dev_mem;
-    uint8_t *vecs = m;              m += round_up_sz((size_t)n * rb, 256);
+    const size_t vec_bytes = index_blocks_max(n, nlist) * tri_block_stride(rb);
+    uint8_t *vecs = m;              m += round_up_sz(vec_bytes, 256);
     float *vnorm = (float *)m;      m += round_up_sz(((size_t)n + TRI_VB) * 4, 256);
     uint32_t *ids = (uint32_t *)m;  m += round_up_sz((size_t)n * 4, 256);
     uint32_t *inv = (uint32_t *)m;  m += round_up_sz((size_t)n * 4, 256);
     uint32_t *loff = (uint32_t *)m; m += round_up_sz(((size_t)nlist + 1) * 4, 256);
+    uint32_t *boff = (uint32_t *)m; m += round_up_sz(((size_t)nlist + 1) * 4, 256);
     uint8_t *cent = m;              m += round_up_sz((size_t)nlist * rb, 256);
     float *cnorm = (float *)m;
 
@@ -919,29 +925,37 @@ extern "C" int ivf_build(tri_pool *P, const ivf_params *p, const void *base, uin
                     ldc, chunk, assign);
     if (rc) return rc;
     HIP_TRY(tri_build_partition(s, assign, n, nlist, block_hist, nblocks, list_len, loff, ids));
-    HIP_TRY(tri_build_invert_perm(s, ids, n, inv));
-    for (uint64_t r0 = 0; r0 < n; r0 += (1u << 20)) {
-        const uint64_t cnt = std::min<uint64_t>(1u << 20, n - r0);
-        HIP_TRY(tri_build_pad_rows(s, dtype, dbase, dim, dim, ids + r0, 0, 0, 1, cnt, vecs + r0 * rb, dpad));
+    HIP_TRY(hipStreamSynchronize(s));
+    std::vector<uint32_t> h_off((size_t)nlist + 1), h_boff((size_t)nlist + 1);
+    HIP_TRY(hipMemcpy(h_off.data(), loff, h_off.size() * 4, hipMemcpyDeviceToHost));
+    if (h_off[nlist] != n) return tri_fail(TRI_EHIP, "partition produced %u rows, expected %llu", h_off[nlist], (unsigned long long)n);
+    // every list in whole blocks of 32 storage slots, the vectors of a block interleaved by 16-byte pieces; slots
+    // behind a list's last vector stay zero
+    h_boff[0] = 0;
+    for (uint32_t l = 0; l < nlist; ++l) h_boff[l + 1] = h_boff[l] + (h_off[l + 1] - h_off[l] + TRI_VB - 1) / TRI_VB;
+    HIP_TRY(hipMemcpy(boff, h_boff.data(), h_boff.size() * 4, hipMemcpyHostToDevice));
+    HIP_TRY(tri_build_slot_map(s, ids, loff, boff, nlist, n, inv));
+    HIP_TRY(hipMemsetAsync(vecs, 0, vec_bytes, s));
+    for (uint64_t r0 = 0; r0 < n; r0 += chunk) {
+        const uint32_t cnt = (uint32_t)std::min<uint64_t>(chunk, n - r0);
+        HIP_TRY(tri_build_pad_rows(s, dtype, dbase, dim, dim, ids + r0, 0, 0, 1, cnt, chunk_rows, dpad));
+        HIP_TRY(tri_build_row_norms(s, dtype, chunk_rows, dpad, cnt, vnorm + r0));
+        HIP_TRY(tri_build_interleave_rows(s, chunk_rows, rb, r0, cnt, ids, inv, vecs));
     }
-    HIP_TRY(tri_build_row_norms(s, dtype, vecs, dpad, n, vnorm));
     HIP_TRY(tri_launch_fill_u32(s, (uint32_t *)(vnorm + n), 0u, TRI_VB));
     HIP_TRY(hipStreamSynchronize(s));
 
     // ---- attach
-    std::vector<uint32_t> h_off((size_t)nlist + 1);
-    HIP_TRY(hipMemcpy(h_off.data(), loff, h_off.size() * 4, hipMemcpyDeviceToHost));
-    if (h_off[nlist] != n) return tri_fail(TRI_EHIP, "partition produced %u rows, expected %llu", h_off[nlist], (unsigned long long)n);
     uint32_t maxlen = 0;
     std::vector<uint32_t> h_len(nlist), h_idx(nlist, id);
     for (uint32_t l = 0; l < nlist; ++l) { h_len[l] = h_off[l + 1] - h_off[l]; maxlen = std::max(maxlen, h_len[l]); }
-    if ((uint64_t)maxlen * rb >= (1ull << 31))
+    if (((uint64_t)maxlen / TRI_VB + 1) * tri_block_stride(rb) >= (1ull << 31))
         return tri_fail(TRI_EINVAL, "longest list (%u vectors of %u bytes) exceeds 2^31 bytes", maxlen, rb);
     tri_index *ix = new (std::nothrow) tri_index();
     if (!ix) return tri_fail(TRI_ENOMEM, "out of host memory");
     ix->pool = P; ix->id = id; ix->p = *p; ix->n = n; ix->dpad = dpad; ix->row_bytes = rb;
     ix->list_base = P->total_lists; ix->max_list_len = maxlen; ix->ids_dev = ids; ix->list_off_dev = loff;
-    ix->dev = TriIndexDev{vecs, vnorm, ids, loff, cent, cnorm, inv, dim, dpad, nlist, p->dtype, rb, ix->list_base, maxlen, 0, n};
+    ix->dev = TriIndexDev{vecs, vnorm, ids, loff, cent, cnorm, inv, boff, dim, dpad, nlist, p->dtype, rb, ix->list_base, maxlen, 0, n};
     hipError_t e = hipMemcpy(P->ws.indexes + id, &ix->dev, sizeof(TriIndexDev), hipMemcpyHostToDevice);
     if (e == hipSuccess) e = hipMemcpy(P->ws.glist_len + ix->list_base, h_len.data(), (size_t)nlist * 4, hipMemcpyHostToDevice);
     if (e == hipSuccess) e = hipMemcpy(P->ws.glist_voff + ix->list_base, h_off.data(), (size_t)nlist * 4, hipMemcpyHostToDevice);

@@ -12,14 +12,23 @@
 #define TRI_KMAX_POW2 1024   // largest k (and nprobe) a selection can return
 
 // One attached index as the kernels see it.  All pointers are device pointers.
+// Stored vectors.  A list occupies whole blocks of TRI_VB = 32 storage slots; inside a block the vectors are
+// interleaved by 16-byte pieces: piece j of the vector in slot i of block b lies at
+//     vecs + b * tri_block_stride(row_bytes) + j * 512 + i * 16,
+// so the 32 pieces that one MFMA operand register of a half-wavefront holds (one piece of each of 32 vectors) are 512
+// contiguous bytes and a wavefront's 16-byte load covers one contiguous KiB.  Slots behind a list's last vector hold
+// zeros.  "Stored position" p numbers the vectors list-major without the padding (ids, vnorm, candidates);
+// "storage slot" = 32 * block + i.  List l starts at block blk_off[l]: the vector at position p of list l is in slot
+// 32 * blk_off[l] + (p - list_off[l]).
 struct TriIndexDev {
-    const void *vecs;        // list-major vectors, row pitch row_bytes, 256-B aligned
+    const void *vecs;        // blocks of 32 interleaved vectors (see above), 256-B aligned
     const float *vnorm;      // |x|^2 per stored vector (list-major order), fp32
     const uint32_t *ids;     // base-row number per stored vector (list-major order)
     const uint32_t *list_off;// [nlist+1] first stored position of each list
     const void *centroids;   // [nlist] rows of pitch row_bytes, index dtype
     const float *cnorm;      // |c|^2 per centroid, fp32
-    const uint32_t *inv;     // stored position of every base row: inv[ids[p]] = p
+    const uint32_t *inv;     // storage slot of every base row
+    const uint32_t *blk_off; // [nlist] first block of each list
     uint32_t dim, dpad, nlist, dtype;
     uint32_t row_bytes;      // dpad * element size, multiple of 128
     uint32_t list_base;      // number of this index's list 0 in the pool-wide list numbering
@@ -27,6 +36,22 @@ struct TriIndexDev {
     uint32_t pad_;
     uint64_t n;
 };
+
+#define TRI_PIECE_PITCH 512u    // bytes between consecutive 16-byte pieces of a stored vector
+// Bytes of one block of 32 stored vectors.  (A pad of 256 bytes behind every block, so that lists do not all start at
+// the same offset modulo a large power of two, made no measurable difference.)
+__host__ __device__ inline uint32_t tri_block_stride(uint32_t row_bytes) { return 32u * row_bytes; }
+
+// First 16-byte piece of the vector in a storage slot; piece j follows at + j * TRI_PIECE_PITCH.
+__device__ __forceinline__ const uint8_t *tri_slot_ptr(const TriIndexDev &ix, uint32_t slot)
+{
+    return (const uint8_t *)ix.vecs + (size_t)(slot >> 5) * tri_block_stride(ix.row_bytes) + (slot & 31u) * 16u;
+}
+// Byte b of that vector.
+__device__ __forceinline__ const uint8_t *tri_slot_byte(const TriIndexDev &ix, uint32_t slot, uint32_t b)
+{
+    return tri_slot_ptr(ix, slot) + (size_t)(b >> 4) * TRI_PIECE_PITCH + (b & 15u);
+}
 
 // Static description of the request in a slot (written at admission).
 struct TriSlotMeta {
@@ -273,7 +298,10 @@ hipError_t tri_build_partition(hipStream_t s, const uint32_t *assign, uint64_t n
                                uint32_t *block_hist /*[nblocks][nlist]*/, uint32_t nblocks,
                                uint32_t *list_len_tmp /*[nlist]*/, uint32_t *list_off /*[nlist+1]*/,
                                uint32_t *perm /*[nrows]*/);
-hipError_t tri_build_invert_perm(hipStream_t s, const uint32_t *ids, uint64_t n, uint32_t *inv);
+hipError_t tri_build_slot_map(hipStream_t s, const uint32_t *ids, const uint32_t *list_off, const uint32_t *blk_off,
+                              uint32_t nlist, uint64_t n, uint32_t *inv /*[n] storage slot of every base row*/);
+hipError_t tri_build_interleave_rows(hipStream_t s, const void *rows /*row-major, pitch row_bytes*/, uint32_t row_bytes,
+                                     uint64_t p0, uint32_t nrows, const uint32_t *ids, const uint32_t *inv, void *vecs);
 hipError_t tri_build_cluster_means(hipStream_t s, int dtype, const void *rows, uint32_t dpad,
                                    const uint32_t *list_off, const uint32_t *perm, uint32_t nlist, int normalise,
                                    float *cent_f32 /*[nlist][dpad] in/out*/);
