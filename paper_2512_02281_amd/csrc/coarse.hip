@@ -178,7 +178,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
     const TriNewDesc *desc = (const TriNewDesc *)(upload + hdr->desc_off);
     coarse_gemm_tile<DT>(upload + hdr->rows_off + g.row_off, ix.row_bytes, g.m, (const uint8_t *)ix.centroids,
                          ix.row_bytes, ix.cnorm, ix.nlist, ix.row_bytes, &desc[g.first_new].metric,
-                         (uint32_t)(sizeof(TriNewDesc) / 4), 0u, C, (ix.nlist + 31u) / 32u * 32u);
+                         (uint32_t)(sizeof(TriNewDesc) / 4), 0u, C, tri_coarse_ldc(ix.nlist));
 }
 
 static hipError_t cg_raise_lds(const void *fn, bool *done)

@@ -548,7 +548,7 @@ struct PqWs {
 PqWs pq_carve(const tri_pq *pq, uint32_t nq, uint8_t *base)
 {
     const TriIndexDev &d = pq->view.dev;
-    const uint32_t ldc = (d.nlist + 31u) / 32u * 32u;
+    const uint32_t ldc = tri_coarse_ldc(d.nlist);
     size_t off = 0;
     auto take = [&](size_t bytes) { uint8_t *p = base ? base + off : nullptr; off += up256(bytes); return p; };
     PqWs w;
@@ -588,7 +588,7 @@ extern "C" int pq_search_batch(tri_pq *pq, const void *queries, size_t pitch_byt
     if (ws_bytes < w.total) return tri_fail(TRI_ENOMEM, "ws has %zu bytes, %zu needed", ws_bytes, w.total);
     PQ_TRY(hipSetDevice(pq->view.device));
     hipStream_t s = pq->view.stream;
-    const uint32_t m = pq->p.m, ldc = (d.nlist + 31u) / 32u * 32u;
+    const uint32_t m = pq->p.m, ldc = tri_coarse_ldc(d.nlist);
     const uint32_t lut_bytes = m * TRI_PQ_KSUB * 4;
     static uint32_t lds_limit = 0;          // (more LDS than a kernel gets by default: raised once per growth)
     if (lut_bytes > lds_limit) {

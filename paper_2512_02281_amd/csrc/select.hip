@@ -660,19 +660,14 @@ __device__ const uint64_t *sel_block_topk(SelShared &sh, const SelSrc &src, SegF
 // fails to isolate a small set (masses of equal scores), go through the general selection.
 #define CSEL_PER 64        // scores per thread the fast path holds in registers: rows of up to 16384 centroids
 
-__global__ __launch_bounds__(TRI_SEL_THREADS) void coarse_select_kernel(
-    const float *__restrict__ scores, const uint8_t *__restrict__ upload, uint32_t gi,
-    const TriIndexDev *__restrict__ indexes, uint32_t *__restrict__ probe, uint32_t nprobe_max)
+// Row `r` of group g by the whole workgroup, any shape (all threads; every return is taken by all of them).
+__device__ void coarse_select_row(SelShared &sh, const float *__restrict__ scores, const uint8_t *__restrict__ upload,
+                                  const TriStepHdr *hdr, const TriCoarseGroup &g, uint32_t r,
+                                  const TriIndexDev *__restrict__ indexes, uint32_t *__restrict__ probe, uint32_t nprobe_max)
 {
-    __shared__ SelShared sh;
-    // (group gi of the step's header: which admission records, which index; surplus workgroups leave)
-    const TriStepHdr *hdr = (const TriStepHdr *)upload;
-    if (gi >= hdr->n_groups) return;
-    const TriCoarseGroup g = hdr->group[gi];
-    if (blockIdx.x >= g.m) return;
-    const uint32_t nlist = indexes[g.index].nlist, ldc = (nlist + 31u) / 32u * 32u;
-    const TriNewDesc d = ((const TriNewDesc *)(upload + hdr->desc_off))[g.first_new + blockIdx.x];
-    const float *row = scores + (size_t)blockIdx.x * ldc;
+    const uint32_t nlist = indexes[g.index].nlist, ldc = tri_coarse_ldc(nlist);
+    const TriNewDesc d = ((const TriNewDesc *)(upload + hdr->desc_off))[g.first_new + r];
+    const float *row = scores + (size_t)r * ldc;
     uint32_t *dst = probe + (size_t)d.slot * nprobe_max;
     const uint32_t tid = threadIdx.x;
     if (nlist <= CSEL_PER * TRI_SEL_THREADS && d.nprobe < nlist) {
@@ -780,14 +775,6 @@ __global__ __launch_bounds__(TRI_SEL_THREADS) void coarse_select_kernel(
     uint32_t n;
     const uint64_t *best = sel_block_topk<false>(sh, src, seg_of, d.nprobe, d.metric, &n);
     for (uint32_t i = tid; i < n; i += TRI_SEL_THREADS) dst[i] = (uint32_t)(best[i] & 0xFFFFFFFFu);
-}
-
-hipError_t tri_launch_coarse_select(const TriLaunchCtx &c, const TriDevWs &ws, uint32_t group, uint32_t grid_m)
-{
-    if (grid_m == 0) return hipSuccess;
-    hipLaunchKernelGGL(coarse_select_kernel, dim3(grid_m), dim3(TRI_SEL_THREADS), 0, c.stream, ws.coarse_scores,
-                       ws.upload, group, ws.indexes, ws.probe, c.nprobe_max);
-    return hipGetLastError();
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -1475,6 +1462,188 @@ __global__ __launch_bounds__(TRI_SEL_THREADS) void slot_merge_block_kernel(const
     if (blockIdx.x == 0 && threadIdx.x == 0) A.rescans[1 + (parity ^ 1u)] = 0;
     const uint32_t queued = A.rescans[1 + parity];
     for (uint32_t i = blockIdx.x; i < queued; i += gridDim.x) merge_block(A, plan[A.merge_queue[i]], sh);   // (uniform)
+}
+
+// ------------------------------------------------------------------------------------------------
+// Coarse selection by one wavefront per newly admitted query (no workgroup barrier anywhere).
+//  pass 1: the row of scores streams through registers, 2048 at a time: load q of chunk c gives lane l the four
+//          scores from c * 2048 + q * 256 + l * 4 on (a wavefront's load reads one contiguous KiB), so the 32 scores
+//          of every 128-byte line sit in eight neighbouring lanes.  The minimum key of each line is taken inside
+//          those eight lanes (three DPP steps) and kept by one of them: up to 512 line minima, each a distinct element
+//          of the row.  The nprobe-th smallest of them, T, is not better than the nprobe-th best of the row (the
+//          nprobe-th best of a subset never is); it is found by bisection on its 32 bits, every count a ballot.
+//  pass 2: only lines whose minimum is not beyond T can hold a key that is not -- nprobe lines or a few more.  They are
+//          listed, each is read again by one lane, and their keys not beyond T (a few dozen) are compacted into LDS by
+//          a prefix count across the lanes, sorted exactly by rank counting and the nprobe best written.
+// The row is read from memory once and an eighth of it twice.  (Reading all of it twice made the kernel wait for
+// HBM: 536 MB per launch at configuration 4, as long as the workgroup kernel before it took.)
+// Rows it cannot settle -- more than CW_CHUNKS * 2048 centroids, more than CW_NPROBE_MAX probes, masses of equal
+// scores -- are queued for coarse_select_kernel.  Word 4 + 64 * parity + group of the counter block holds the number
+// of queued rows of that group; the rows of group g are queued from g.first_new on.
+#define CW_CHUNKS 8
+#define CW_LINES (CW_CHUNKS * 64)       // 128-byte lines of a row the kernel can hold minima of
+#define CW_NPROBE_MAX 128
+#define CSEL_QHEAD(parity, gi) (4u + 64u * (parity) + (gi))
+
+struct CoarseWaveLds {
+    uint64_t a[MRG_CAP], b[MRG_CAP];
+    uint16_t line[CW_LINES];            // lines to read again
+};
+
+// Minimum over the eight lanes 8 * (l / 8) .. + 7: quad butterfly, then the mirror image inside the half row.
+__device__ __forceinline__ uint32_t cw_min8(uint32_t v)
+{
+    uint32_t o = (uint32_t)__builtin_amdgcn_update_dpp((int)v, (int)v, 0xB1, 0xF, 0xF, false);    // quad_perm [1,0,3,2]
+    v = o < v ? o : v;
+    o = (uint32_t)__builtin_amdgcn_update_dpp((int)v, (int)v, 0x4E, 0xF, 0xF, false);             // quad_perm [2,3,0,1]
+    v = o < v ? o : v;
+    o = (uint32_t)__builtin_amdgcn_update_dpp((int)v, (int)v, 0x141, 0xF, 0xF, false);            // row_half_mirror
+    return o < v ? o : v;
+}
+
+__global__ __launch_bounds__(TRI_SEL_THREADS) __attribute__((amdgpu_waves_per_eu(4, 4))) void coarse_select_wave_kernel(
+    const float *__restrict__ scores, const uint8_t *__restrict__ upload, uint32_t gi,
+    const TriIndexDev *__restrict__ indexes, uint32_t *__restrict__ probe, uint32_t nprobe_max,
+    uint32_t *__restrict__ counters, uint32_t *__restrict__ queue)
+{
+    constexpr uint32_t NW = TRI_SEL_THREADS / 64;
+    __shared__ CoarseWaveLds wv[NW];
+    // (the wavefront's number as a scalar: everything that depends on the row -- the descriptor of its scores first of
+    // all -- is then uniform for the compiler too)
+    const uint32_t lane = threadIdx.x & 63, wave = (uint32_t)__builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
+    // (group gi of the step's header: which admission records, which index; surplus wavefronts leave)
+    const TriStepHdr *hdr = (const TriStepHdr *)upload;
+    if (gi >= hdr->n_groups) return;
+    const TriCoarseGroup g = hdr->group[gi];
+    const uint32_t r = blockIdx.x * NW + wave;
+    if (r >= g.m) return;
+    const uint32_t nlist = indexes[g.index].nlist, ldc = tri_coarse_ldc(nlist);
+    const TriNewDesc d = ((const TriNewDesc *)(upload + hdr->desc_off))[g.first_new + r];
+    uint32_t *dst = probe + (size_t)d.slot * nprobe_max;
+    CoarseWaveLds &L = wv[wave];
+    auto defer = [&]() {                                              // (all lanes of the wavefront take the same way)
+        if (lane == 0) queue[g.first_new + atomicAdd(&counters[CSEL_QHEAD(hdr->coarse_parity, gi)], 1u)] = r;
+    };
+    if (nlist > CW_LINES * 32u || d.nprobe >= nlist || d.nprobe > CW_NPROBE_MAX) { defer(); return; }
+    // (loads through a descriptor that ends with the row: past its end they return zeros, which the padding mask covers)
+    const __amdgpu_buffer_rsrc_t rrs =
+        __builtin_amdgcn_make_buffer_rsrc((void *)(scores + (size_t)r * ldc), 0, nlist * 4u, 0x00020000);
+    typedef unsigned int cw_u32x4 __attribute__((ext_vector_type(4)));
+    // keys of the four scores from element e0 on (all-ones: padding past the row's end)
+    auto keys_of = [&](const cw_u32x4 &v, uint32_t e0, uint32_t (&k)[4]) {
+        const uint32_t raw[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+        for (int j = 0; j < 4; ++j) k[j] = sel_key(__uint_as_float(raw[j]), d.metric) | (e0 + j < nlist ? 0u : 0xFFFFFFFFu);
+    };
+    const uint32_t nchunks = (nlist + 2047u) / 2048u;                 // (uniform)
+    uint32_t m[CW_CHUNKS];                                            // minimum of line c * 64 + (l % 8) * 8 + l / 8
+    // (the loads of chunk c + 1 are issued before chunk c is worked on; a chunk past the row's end costs no memory
+    // access and is skipped)
+    cw_u32x4 v[2][8];
+#pragma unroll
+    for (int q = 0; q < 8; ++q) v[0][q] = __builtin_amdgcn_raw_buffer_load_b128(rrs, lane * 16u, q * 1024u, 0);
+#pragma unroll
+    for (int c = 0; c < CW_CHUNKS; ++c) {
+        if (c + 1 < CW_CHUNKS) {
+#pragma unroll
+            for (int q = 0; q < 8; ++q)
+                v[(c + 1) & 1][q] = __builtin_amdgcn_raw_buffer_load_b128(rrs, lane * 16u, (c + 1) * 8192u + q * 1024u, 0);
+        }
+        m[c] = 0xFFFFFFFFu;
+        if ((uint32_t)c < nchunks) {
+#pragma unroll
+            for (int q = 0; q < 8; ++q) {
+                uint32_t k[4];
+                keys_of(v[c & 1][q], c * 2048u + q * 256u + lane * 4u, k);
+                uint32_t mn = k[0] < k[1] ? k[0] : k[1];
+                const uint32_t mn2 = k[2] < k[3] ? k[2] : k[3];
+                mn = cw_min8(mn < mn2 ? mn : mn2);
+                m[c] = (lane & 7u) == (uint32_t)q ? mn : m[c];
+            }
+        }
+    }
+    uint32_t T = 0;
+    for (int b = 31; b >= 0; --b) {
+        const uint32_t trial = T | ((1u << b) - 1u);                  // (bit b clear, every lower bit set)
+        uint32_t cnt = 0;
+#pragma unroll
+        for (int c = 0; c < CW_CHUNKS; ++c) cnt += (uint32_t)__popcll(__ballot(m[c] <= trial));
+        if (cnt < d.nprobe) T |= 1u << b;
+    }
+    if (T == 0xFFFFFFFFu) { defer(); return; }                        // (fewer than nprobe minima that are not padding)
+    // the lines to read again
+    uint32_t mine = 0;
+#pragma unroll
+    for (int c = 0; c < CW_CHUNKS; ++c) mine += m[c] <= T ? 1u : 0u;
+    const uint32_t incl = thr_wave_scan(mine, 0u, [](uint32_t a, uint32_t b2) { return a + b2; });
+    const uint32_t nlines = (uint32_t)__builtin_amdgcn_readlane((int)incl, 63);
+    {
+        uint32_t pos = incl - mine;
+#pragma unroll
+        for (int c = 0; c < CW_CHUNKS; ++c)
+            if (m[c] <= T) L.line[pos++] = (uint16_t)(c * 64u + (lane & 7u) * 8u + (lane >> 3));
+    }
+    thr_wave_fence();
+    uint32_t total = 0;
+    for (uint32_t l0 = 0; l0 < nlines; l0 += 64) {                    // (nlines >= nprobe; one round unless scores tie in masses)
+        const bool have = l0 + lane < nlines;
+        const uint32_t e0 = have ? (uint32_t)L.line[l0 + lane] * 32u : 0xFFFFFFE0u;    // (no line: out of range, padding keys)
+        cw_u32x4 v[8];
+#pragma unroll
+        for (int q = 0; q < 8; ++q) v[q] = __builtin_amdgcn_raw_buffer_load_b128(rrs, e0 * 4u, q * 16u, 0);
+        uint32_t k[8][4];
+        uint32_t cnt = 0;
+#pragma unroll
+        for (int q = 0; q < 8; ++q) {
+            keys_of(v[q], e0 + q * 4u, k[q]);
+#pragma unroll
+            for (int j = 0; j < 4; ++j) cnt += have && k[q][j] <= T ? 1u : 0u;
+        }
+        const uint32_t inc2 = thr_wave_scan(cnt, 0u, [](uint32_t a, uint32_t b2) { return a + b2; });
+        uint32_t pos = total + inc2 - cnt;
+        total += (uint32_t)__builtin_amdgcn_readlane((int)inc2, 63);
+        if (total > MRG_CAP) break;                                   // (uniform)
+#pragma unroll
+        for (int q = 0; q < 8; ++q)
+#pragma unroll
+            for (int j = 0; j < 4; ++j)
+                if (have && k[q][j] <= T) L.a[pos++] = ((uint64_t)k[q][j] << 32) | (e0 + q * 4u + j);
+    }
+    if (total > MRG_CAP) { defer(); return; }
+    mrg_rank_sort(L.a, total, L.b, lane);
+    for (uint32_t i = lane; i < d.nprobe; i += 64) dst[i] = (uint32_t)(L.b[i] & 0xFFFFFFFFu);
+}
+
+// The rows the kernel above queued, dealt out among a fixed number of workgroups.  The queue heads come in two sets,
+// used in turn by the steps that admit queries: the first group's launch of a step puts the other set back to zero
+// (its last readers, the launches of the previous such step, have finished).
+__global__ __launch_bounds__(TRI_SEL_THREADS) void coarse_select_kernel(
+    const float *__restrict__ scores, const uint8_t *__restrict__ upload, uint32_t gi,
+    const TriIndexDev *__restrict__ indexes, uint32_t *__restrict__ probe, uint32_t nprobe_max,
+    uint32_t *__restrict__ counters, const uint32_t *__restrict__ queue)
+{
+    __shared__ SelShared sh;
+    const TriStepHdr *hdr = (const TriStepHdr *)upload;
+    if (gi >= hdr->n_groups) return;
+    if (gi == 0 && blockIdx.x == 0 && threadIdx.x < TRI_MAX_COARSE_GROUPS)
+        counters[CSEL_QHEAD(hdr->coarse_parity ^ 1u, threadIdx.x)] = 0u;
+    const TriCoarseGroup g = hdr->group[gi];
+    const uint32_t nq = counters[CSEL_QHEAD(hdr->coarse_parity, gi)];
+    for (uint32_t qi = blockIdx.x; qi < nq; qi += gridDim.x) {
+        coarse_select_row(sh, scores, upload, hdr, g, queue[g.first_new + qi], indexes, probe, nprobe_max);
+        __syncthreads();                                              // (the workgroup's next row reuses sh)
+    }
+}
+
+hipError_t tri_launch_coarse_select(const TriLaunchCtx &c, const TriDevWs &ws, uint32_t group, uint32_t grid_m)
+{
+    if (grid_m == 0) return hipSuccess;
+    constexpr uint32_t NW = TRI_SEL_THREADS / 64;
+    hipLaunchKernelGGL(coarse_select_wave_kernel, dim3((grid_m + NW - 1) / NW), dim3(TRI_SEL_THREADS), 0, c.stream,
+                       ws.coarse_scores, ws.upload, group, ws.indexes, ws.probe, c.nprobe_max, ws.rescans, ws.coarse_queue);
+    hipLaunchKernelGGL(coarse_select_kernel, dim3(grid_m < 256u ? grid_m : 256u), dim3(TRI_SEL_THREADS), 0, c.stream,
+                       ws.coarse_scores, ws.upload, group, ws.indexes, ws.probe, c.nprobe_max, ws.rescans, ws.coarse_queue);
+    return hipGetLastError();
 }
 
 hipError_t tri_launch_merge(const TriLaunchCtx &c, const TriDevWs &ws, uint32_t grid_plan, bool keep_probes)

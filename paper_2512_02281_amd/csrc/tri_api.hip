@@ -166,6 +166,7 @@ struct tri_pool {
     uint32_t n_running = 0;
     uint64_t admit_seq = 0, step_seq = 0;
     uint32_t merge_launches = 0;      // parity of the merge kernels' queue heads
+    uint32_t coarse_steps = 0;        // parity of the coarse selection's queue heads
     StepRec ring[RING];
     uint8_t *pinned = nullptr;         // upload / result blocks of the steps in flight, then the query store
     bool own_pinned = false;           // allocated here (hipHostMalloc) and freed in tri_pool_destroy
@@ -249,8 +250,9 @@ size_t carve(const tri_pool_cfg &c, uint32_t max_row_bytes, uint32_t coarse_rows
     CARVE(slot_cand_off, uint32_t *, S * 4)
     CARVE(slot_cand_cap, uint32_t *, S * 4)
     CARVE(slot_cand_cnt, uint32_t *, S * 4)
-    CARVE(rescans, uint32_t *, 256)
+    CARVE(rescans, uint32_t *, 1024)
     CARVE(merge_queue, uint32_t *, S * 4)
+    CARVE(coarse_queue, uint32_t *, S * 4)
     CARVE(step_dev, TriStepDev *, 256)
     CARVE(cand, uint2 *, (size_t)score_capacity * 4)
     // (res_block / res_probes point into the pinned host block of the step in flight: set per step)
@@ -280,7 +282,7 @@ int derive(const tri_pool_cfg *c, uint32_t *max_row_bytes, uint32_t *coarse_rows
         return tri_fail(TRI_EINVAL, "slots * padded row bytes must stay below 2^31");
     *coarse_rows = c->coarse_rows ? c->coarse_rows : 1024u;
     if (*coarse_rows > c->slots) *coarse_rows = c->slots;
-    *coarse_ldc = round_up(c->max_nlist, 32u);
+    *coarse_ldc = tri_coarse_ldc(c->max_nlist);
     // default: room for 1024 kept candidates per slot and 32 per work item (2 words each)
     *score_capacity = c->score_capacity ? c->score_capacity : 2ull * ((uint64_t)c->slots * 1024u + (uint64_t)c->items_per_step * 32u);
     if (*score_capacity > (1ull << 32))      // candidate pairs are addressed with 32-bit pair numbers
@@ -566,7 +568,7 @@ extern "C" int tri_pool_create(const tri_pool_cfg *cfg, void *dev_ws, size_t dev
         P->own_pinned = true;
     }
     // what must start at zero: the rescan counter and the merge kernels' queue heads; the items-per-list histogram
-    e = tri_launch_fill_u32(P->stream, P->ws.rescans, 0u, 4);
+    e = tri_launch_fill_u32(P->stream, P->ws.rescans, 0u, 256);
     if (e == hipSuccess) e = tri_launch_fill_u32(P->stream, P->ws.hist, 0u, cfg->max_total_lists);
     if (e == hipSuccess) e = hipStreamSynchronize(P->stream);
     if (e != hipSuccess) { tri_pool_destroy(P); return tri_fail(TRI_EHIP, "workspace set-up -> %s", hipGetErrorString(e)); }
@@ -733,7 +735,7 @@ BuildTmp build_tmp(const ivf_params &p, uint64_t n, bool base_on_host)
 {
     BuildTmp t{};
     const uint32_t es = esize(p.dtype), dpad = dpad_of(p.dim, p.dtype), rb = dpad * es;
-    t.ldc = round_up(p.nlist, 32);
+    t.ldc = tri_coarse_ldc(p.nlist);
     t.chunk = round_up((uint32_t)std::min<uint64_t>(n, std::max<uint64_t>(128, (256ull << 20) / t.ldc)), 128);
     t.nblocks = (uint32_t)std::min<uint64_t>(512, (n + 255) / 256);
     t.ns = p.train_iters ? (n <= 256ull * p.nlist ? n : 256ull * p.nlist) : 0;
@@ -1454,6 +1456,7 @@ int step_locked(tri_pool *P, tri_step_stats *st)
         a = b;
     }
     hdr_h->n_groups = n_groups;
+    hdr_h->coarse_parity = n_groups ? (P->coarse_steps++ & 1u) : 0u;   // (the coarse kernels act when the step admits queries)
     hdr_h->merge_parity = n_plan ? (P->merge_launches++ & 1u) : 0u;   // (the merge kernels run when the step has a plan)
 
     if (P->inject_failure) {

@@ -99,7 +99,8 @@ struct TriStepHdr {
     uint32_t rows_off;       // row area (filled on the device by the admit kernel)
     uint32_t n_groups;
     uint32_t merge_parity;   // which of the two queue heads of the merge kernels this step uses (alternates with every merge launch)
-    uint32_t pad_[6];
+    uint32_t coarse_parity;  // which set of queue heads the coarse selection of this step uses (alternates with every step that admits queries)
+    uint32_t pad_[5];
     TriCoarseGroup group[TRI_MAX_COARSE_GROUPS];
 };
 static_assert(sizeof(TriStepHdr) == 1024, "header is 1024 bytes");
@@ -202,6 +203,8 @@ struct TriDevWs {
                               // [1], [2]: entries in merge_queue, one head for each parity of the merge launches (a launch
                               // fills and reads its own and clears the other)
     uint32_t *merge_queue;    // [S] plan entries of the step that the one-wavefront merge did not settle
+    uint32_t *coarse_queue;   // [S] rows of the step's coarse groups that the one-wavefront selection did not settle (group g from g.first_new on);
+                              // their counts: words 4 + 64 * parity + group of `rescans`
     TriStepDev *step_dev;     // [1]
     uint2 *cand;              // [score_capacity / 2] candidate buffer: (score bits, stored position) pairs
     // results of retiring slots, compact, per step
@@ -274,6 +277,10 @@ __host__ __device__ inline uint32_t tri_chunk_vecs(uint32_t len, uint32_t min_ch
     c = (c + TRI_VB - 1) / TRI_VB * TRI_VB;
     return c > min_chunk ? c : min_chunk;
 }
+
+// Row pitch (in scores) of a coarse score block over nlist centroids: whole 128-byte lines.  (256 bytes more per row,
+// so that rows do not all start at the same offset modulo 64 KiB, made no measurable difference.)
+__host__ __device__ inline uint32_t tri_coarse_ldc(uint32_t nlist) { return (nlist + 31u) / 32u * 32u; }
 
 // Which scan kernel serves an index: 5 classes per storage type (other, 512, 1024, 1536, 2048 bytes per row).
 __host__ __device__ inline uint32_t tri_scan_class(uint32_t dtype, uint32_t row_bytes)

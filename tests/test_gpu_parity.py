@@ -901,6 +901,46 @@ def test_massive_ties_take_the_exact_path():
             harness.compare_with_oracle(oidx, base, queries, k, nprobe, metric, ids, dist, n_out, probes, strict=True)
 
 
+def test_every_path_of_the_coarse_selection():
+    """The probe list of a new query is chosen by one wavefront when its one pass settles the row, and by the general
+    workgroup selection when it does not; rows of the second kind are queued, with queue heads that alternate between
+    the steps.  Two indexes in one pool (two coarse groups in every step): one with distinct centroids, one whose 640
+    centroids are 5 prototypes repeated 128 times -- every score ties 128 times, far more equal keys than the
+    wavefront's pool holds, so those rows are deferred and must come out with the tie rule (smaller centroid number
+    first) intact.  Few slots, so that many consecutive steps admit queries of both kinds; nprobe from 1 to above the
+    wavefront path's limit; probe lists and results against the oracle, strictly (integer-valued data)."""
+    tri = harness.lib()
+    rng = np.random.default_rng(55)
+    dim = 16
+    cent_a = rng.integers(-8, 9, size=(700, dim)).astype(np.float32)              # (700: the row ends inside a 128-byte line)
+    protos = rng.integers(-8, 9, size=(5, dim)).astype(np.float32)
+    cent_b = protos[np.arange(640) % 5]
+    base_a = (cent_a[rng.integers(0, 700, size=20_000)] + rng.integers(-1, 2, size=(20_000, dim))).astype(np.float32)
+    base_b = (cent_b[rng.integers(0, 640, size=12_000)] + rng.integers(-1, 2, size=(12_000, dim))).astype(np.float32)
+    nq = 60
+    qa = (cent_a[rng.integers(0, 700, size=nq)] + rng.integers(-1, 2, size=(nq, dim))).astype(np.float32)
+    qb = (protos[rng.integers(0, 5, size=nq)] + rng.integers(-1, 2, size=(nq, dim))).astype(np.float32)
+    k = np.full(nq, 10, dtype=np.uint32)
+    nprobe = np.array([1, 7, 32, 64, 128, 129, 200], dtype=np.uint32)[np.arange(nq) % 7]
+    metric = (np.arange(nq) // 3 % 2).astype(np.uint32)
+    with harness.default_pool(tri, slots=6, items_per_step=6 * 256, kmax=16, nprobe_max=256, max_dim=dim, max_nlist=704,
+                              max_total_lists=1344, max_indexes=2, score_capacity=8 << 20) as pool:
+        ia = pool.build_index(base_a, dim, 700, tri.TRI_F32, tri.TRI_L2, 0, centroids=cent_a)
+        ib = pool.build_index(base_b, dim, 640, tri.TRI_F32, tri.TRI_L2, 0, centroids=cent_b)
+        oa, ob = harness.oracle_index(tri, ia, base_a), harness.oracle_index(tri, ib, base_b)
+        q = []
+        for i in range(nq):                                                       # (interleaved: both groups in every step)
+            q.append(tri.make_queries(ia, qa[i:i + 1], k[i:i + 1], nprobe[i:i + 1], metric[i:i + 1]))
+            q.append(tri.make_queries(ib, qb[i:i + 1], k[i:i + 1], nprobe[i:i + 1], metric[i:i + 1]))
+        ids, dist, n_out, probes, stats = harness.run_all(tri, pool, np.concatenate(q))
+        ra = harness.compare_with_oracle(oa, base_a, qa, k, nprobe, metric, ids[0::2], dist[0::2], n_out[0::2],
+                                         [probes[i] for i in range(0, 2 * nq, 2)] if probes is not None else None, strict=True)
+        rb = harness.compare_with_oracle(ob, base_b, qb, k, nprobe, metric, ids[1::2], dist[1::2], n_out[1::2],
+                                         [probes[i] for i in range(1, 2 * nq, 2)] if probes is not None else None, strict=True)
+        _say(f"coarse selection paths: {len(stats)} steps, distinct centroids {ra}, repeated centroids {rb}")
+        assert len(stats) >= 15
+
+
 def test_several_threads_submit_while_one_steps():
     """search_submit_batch is safe from several threads while one driver thread steps and polls: four
     submitters feed their shares in small chunks; every query is answered once and as the oracle says."""
