@@ -1,7 +1,7 @@
 // What a plain streaming read achieves on this GPU: the context figure beside the vendor's peak that the
 // list scan's bandwidth is quoted against (the paper's Sec. 2 roofline takes the memory bandwidth as given).
 // Grid-stride reads of 16 bytes per lane, U in flight per lane, nothing else; the best of a few launch shapes
-// (U = 8 or 16 loads in flight, 4, 8 or 16 workgroups per compute unit) is reported.
+// (U = 8 or 16 loads in flight, 4, 8 or 16 workgroups per compute unit, plain or non-temporal loads) is reported.
 #include "../../include/trinity_ivf.h"
 #include "tri_common.h"
 
@@ -9,7 +9,17 @@
 
 namespace {
 
-template <int U>
+typedef unsigned int probe_u32x4 __attribute__((ext_vector_type(4)));
+
+template <bool NT>
+__device__ __forceinline__ uint4 probe_ld(const uint4 *p)
+{
+    if (!NT) return *p;
+    const probe_u32x4 v = __builtin_nontemporal_load((const probe_u32x4 *)p);
+    return make_uint4(v.x, v.y, v.z, v.w);
+}
+
+template <int U, bool NT>
 __global__ __launch_bounds__(256) void stream_read_kernel(const uint4 *__restrict__ p, size_t n16, uint32_t *__restrict__ sink)
 {
     const size_t tid = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
@@ -19,11 +29,11 @@ __global__ __launch_bounds__(256) void stream_read_kernel(const uint4 *__restric
     for (; i + (U - 1) * stride < n16; i += U * stride) {
         uint4 v[U];
 #pragma unroll
-        for (int u = 0; u < U; ++u) v[u] = p[i + u * stride];
+        for (int u = 0; u < U; ++u) v[u] = probe_ld<NT>(p + i + u * stride);
 #pragma unroll
         for (int u = 0; u < U; ++u) acc ^= v[u].x ^ v[u].y ^ v[u].z ^ v[u].w;
     }
-    for (; i < n16; i += stride) { const uint4 v = p[i]; acc ^= v.x ^ v.y ^ v.z ^ v.w; }
+    for (; i < n16; i += stride) { const uint4 v = probe_ld<NT>(p + i); acc ^= v.x ^ v.y ^ v.z ^ v.w; }
     if (acc == 0x9E3779B9u) sink[0] = acc;         // (keeps the loads alive; practically never taken)
 }
 
@@ -45,12 +55,14 @@ extern "C" int tri_stream_read_bandwidth(const void *dev_buf, size_t bytes, void
     const size_t n16 = bytes / 16;
     const dim3 block(256);
     double best = 0.0;
-    for (int shape = 0; shape < 6 && e == hipSuccess; ++shape) {
+    for (int shape = 0; shape < 12 && e == hipSuccess; ++shape) {
         const dim3 grid((unsigned)prop.multiProcessorCount * (4u << (shape % 3)));
-        const bool wide = shape >= 3;
+        const bool wide = shape % 6 >= 3, nt = shape >= 6;
         auto launch = [&]() {
-            if (wide) hipLaunchKernelGGL(stream_read_kernel<16>, grid, block, 0, s, (const uint4 *)dev_buf, n16, (uint32_t *)dev_sink);
-            else hipLaunchKernelGGL(stream_read_kernel<8>, grid, block, 0, s, (const uint4 *)dev_buf, n16, (uint32_t *)dev_sink);
+            if (wide && nt) hipLaunchKernelGGL((stream_read_kernel<16, true>), grid, block, 0, s, (const uint4 *)dev_buf, n16, (uint32_t *)dev_sink);
+            else if (wide) hipLaunchKernelGGL((stream_read_kernel<16, false>), grid, block, 0, s, (const uint4 *)dev_buf, n16, (uint32_t *)dev_sink);
+            else if (nt) hipLaunchKernelGGL((stream_read_kernel<8, true>), grid, block, 0, s, (const uint4 *)dev_buf, n16, (uint32_t *)dev_sink);
+            else hipLaunchKernelGGL((stream_read_kernel<8, false>), grid, block, 0, s, (const uint4 *)dev_buf, n16, (uint32_t *)dev_sink);
         };
         float ms = 0.f;
         launch();                                                   // warm-up

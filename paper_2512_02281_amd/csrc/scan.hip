@@ -58,9 +58,14 @@
 
 typedef unsigned int scan_u32x4 __attribute__((ext_vector_type(4)));
 
+// 16 bytes of a list.  NT: the load is marked non-temporal -- for an index far larger than the last-level cache the
+// lists only pass through, and keeping them out of the caches leaves those to the query rows (configuration 4's
+// main launch: 5.74 -> 6.36 TB/s); for an index of a few GB, a tenth of which the cache still serves from step to
+// step, it costs that tenth.
+template <bool NT = false>
 __device__ __forceinline__ uint4 scan_ld16(__amdgpu_buffer_rsrc_t rs, uint32_t off)
 {
-    const scan_u32x4 v = __builtin_amdgcn_raw_buffer_load_b128(rs, off, 0, 0);
+    const scan_u32x4 v = __builtin_amdgcn_raw_buffer_load_b128(rs, off, 0, NT ? 2 : 0);
     return make_uint4(v.x, v.y, v.z, v.w);
 }
 
@@ -168,7 +173,7 @@ __device__ __forceinline__ void scan_stage_flush(const uint2 *stage, uint32_t &s
 // NG = 128-byte groups per row, RG = groups held in the register ring (NG % RG == 0): while group g
 // of a block is multiplied, the loads of the group RG steps ahead -- in this block or the next --
 // are in flight.
-template <int DT, int NG, int RG, bool FILTER>
+template <int DT, int NG, int RG, bool FILTER, bool NT>
 __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(1, 1))) void scan_wave_kernel(
     const TriTile *__restrict__ tiles, const uint32_t *__restrict__ n_tiles_ptr, uint32_t *__restrict__ tile_counter,
     uint32_t my_class, const uint32_t *__restrict__ sorted_slot, const uint8_t *__restrict__ slot_query,
@@ -218,7 +223,7 @@ __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(1, 1))) void
 #pragma unroll
             for (int g = 0; g < RG; ++g) {
 #pragma unroll
-                for (int c = 0; c < 4; ++c) buf[g][c] = scan_ld16(vrs, off + g * 4096 + c * 1024);
+                for (int c = 0; c < 4; ++c) buf[g][c] = scan_ld16<NT>(vrs, off + g * 4096 + c * 1024);
                 __builtin_amdgcn_sched_barrier(0);
             }
             // this lane's query (row l%32 of the first MFMA operand): its vector as operand pieces; a
@@ -288,7 +293,7 @@ __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(1, 1))) void
                     __builtin_amdgcn_sched_barrier(0);
                     const uint32_t nxt = g + RG < NG ? off + (g + RG) * 4096 : off_next + (g + RG - NG) * 4096;
 #pragma unroll
-                    for (int c = 0; c < 4; ++c) buf[sl][c] = scan_ld16(vrs, nxt + c * 1024);
+                    for (int c = 0; c < 4; ++c) buf[sl][c] = scan_ld16<NT>(vrs, nxt + c * 1024);
                     __builtin_amdgcn_sched_barrier(0);
                 }
                 off = off_next;
@@ -600,22 +605,28 @@ struct ScanVariant {
 };
 
 // class = storage type * 5 + (0: other row length, 1..4: 512, 1024, 1536, 2048 bytes per row)
-template <bool FILTER>
-static ScanVariant scan_variant(uint32_t klass)
+template <bool FILTER, bool NT>
+static ScanVariant scan_variant_nt(uint32_t klass)
 {
     switch (klass) {
     case 0: return {scan_lds_kernel<TRI_DT_F32, 0, FILTER>, false};
-    case 1: return {scan_wave_kernel<TRI_DT_F32, 4, 4, FILTER>, true};
-    case 2: return {scan_wave_kernel<TRI_DT_F32, 8, 4, FILTER>, true};
+    case 1: return {scan_wave_kernel<TRI_DT_F32, 4, 4, FILTER, NT>, true};
+    case 2: return {scan_wave_kernel<TRI_DT_F32, 8, 4, FILTER, NT>, true};
     case 3: return {scan_lds_kernel<TRI_DT_F32, 12, FILTER>, false};   // (the register-resident form spills for fp32 rows this
                                                                         //  wide, whatever the ring length: 150-350 bytes per lane)
     case 4: return {scan_lds_kernel<TRI_DT_F32, 16, FILTER>, false};
     case 5: return {scan_lds_kernel<TRI_DT_F16, 0, FILTER>, false};
-    case 6: return {scan_wave_kernel<TRI_DT_F16, 4, 4, FILTER>, true};
-    case 7: return {scan_wave_kernel<TRI_DT_F16, 8, 4, FILTER>, true};
-    case 8: return {scan_wave_kernel<TRI_DT_F16, 12, 6, FILTER>, true};
-    default: return {scan_wave_kernel<TRI_DT_F16, 16, 4, FILTER>, true};   // (2048-byte fp16 rows: 256 query registers + a 4-group ring still fit)
+    case 6: return {scan_wave_kernel<TRI_DT_F16, 4, 4, FILTER, NT>, true};
+    case 7: return {scan_wave_kernel<TRI_DT_F16, 8, 4, FILTER, NT>, true};
+    case 8: return {scan_wave_kernel<TRI_DT_F16, 12, 6, FILTER, NT>, true};
+    default: return {scan_wave_kernel<TRI_DT_F16, 16, 4, FILTER, NT>, true};   // (2048-byte fp16 rows: 256 query registers + a 4-group ring still fit)
     }
+}
+
+template <bool FILTER>
+static ScanVariant scan_variant(uint32_t klass, bool nt = false)
+{
+    return nt ? scan_variant_nt<FILTER, true>(klass) : scan_variant_nt<FILTER, false>(klass);
 }
 
 static uint32_t g_scan_lds_limit[2 * TRI_SCAN_CLASSES] = {};
@@ -659,7 +670,7 @@ hipError_t tri_launch_scan(const TriLaunchCtx &c, const TriDevWs &ws, uint32_t m
     void *out = sample ? (void *)ws.sample_scores : (void *)ws.cand;
     for (uint32_t k = 0; k < TRI_SCAN_CLASSES; ++k) {
         if (!(class_mask & (1u << k))) continue;
-        const ScanVariant v = sample ? scan_variant<false>(k) : scan_variant<true>(k);
+        const ScanVariant v = sample ? scan_variant<false>(k, c.scan_nt != 0) : scan_variant<true>(k, c.scan_nt != 0);
         uint32_t *counter = ws.tile_counter + (sample ? TRI_SCAN_CLASSES : 0) + k;
         if (v.wave) {
             // one wavefront per SIMD: 4 per compute unit

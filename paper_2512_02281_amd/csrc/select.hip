@@ -1541,13 +1541,13 @@ __global__ __launch_bounds__(TRI_SEL_THREADS) __attribute__((amdgpu_waves_per_eu
     // access and is skipped)
     cw_u32x4 v[2][8];
 #pragma unroll
-    for (int q = 0; q < 8; ++q) v[0][q] = __builtin_amdgcn_raw_buffer_load_b128(rrs, lane * 16u, q * 1024u, 0);
+    for (int q = 0; q < 8; ++q) v[0][q] = __builtin_amdgcn_raw_buffer_load_b128(rrs, lane * 16u, q * 1024u, 2);   // (read once: non-temporal)
 #pragma unroll
     for (int c = 0; c < CW_CHUNKS; ++c) {
         if (c + 1 < CW_CHUNKS) {
 #pragma unroll
             for (int q = 0; q < 8; ++q)
-                v[(c + 1) & 1][q] = __builtin_amdgcn_raw_buffer_load_b128(rrs, lane * 16u, (c + 1) * 8192u + q * 1024u, 0);
+                v[(c + 1) & 1][q] = __builtin_amdgcn_raw_buffer_load_b128(rrs, lane * 16u, (c + 1) * 8192u + q * 1024u, 2);
         }
         m[c] = 0xFFFFFFFFu;
         if ((uint32_t)c < nchunks) {

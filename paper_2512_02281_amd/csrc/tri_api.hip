@@ -554,7 +554,7 @@ extern "C" int tri_pool_create(const tri_pool_cfg *cfg, void *dev_ws, size_t dev
     P->max_row_bytes = mrb; P->coarse_rows = cr; P->coarse_ldc = ldc; P->score_capacity = sc; P->upload_bytes = up;
     carve(*cfg, mrb, cr, ldc, sc, up, (uint8_t *)dev_ws, &P->ws);
     P->ctx = TriLaunchCtx{P->stream, cfg->slots, cfg->items_per_step, cfg->kmax, cfg->nprobe_max,
-                          cfg->max_total_lists, mrb, (uint32_t)prop.multiProcessorCount};
+                          cfg->max_total_lists, mrb, (uint32_t)prop.multiProcessorCount, 0u};
     // pinned staging for RING steps and the query store: the caller's, or allocated here
     const size_t S = cfg->slots;
     P->down_probe_off = L.blk;
@@ -785,6 +785,15 @@ int assign_all(hipStream_t s, int dtype, uint32_t dim, uint32_t dpad, uint32_t r
 }
 }  // namespace
 
+// Lists are streamed past the caches once the attached vectors are far more than the caches hold.
+static void set_scan_nt(tri_pool *P)
+{
+    uint64_t bytes = 0;
+    for (const tri_index *o : P->indexes)
+        if (o) bytes += o->n * o->row_bytes;
+    P->ctx.scan_nt = bytes >= TRI_NT_INDEX_BYTES ? 1u : 0u;
+}
+
 extern "C" int ivf_build_tmp_bytes(const ivf_params *p, uint64_t n, int base_on_host, size_t *tmp_bytes)
 {
     size_t unused = 0;
@@ -970,6 +979,7 @@ extern "C" int ivf_build(tri_pool *P, const ivf_params *p, const void *base, uin
     P->total_lists += nlist;
     P->attached_row_bytes = std::max(P->attached_row_bytes, rb);
     P->scan_class_mask |= 1u << tri_scan_class(p->dtype, rb);
+    set_scan_nt(P);
     drop_graphs(P);                    // (recorded steps cover the indexes attached when they were recorded)
     *out = ix;
     return TRI_OK;
@@ -1048,6 +1058,7 @@ extern "C" int ivf_destroy(tri_index *ix)
         }
     if (ix->list_base + ix->p.nlist == P->total_lists) P->total_lists = ix->list_base;   // last attached: give its list range back
     delete ix;
+    set_scan_nt(P);
     drop_graphs(P);
     return P->failed ? TRI_OK : upload_scan_order(P);
 }
