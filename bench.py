@@ -151,10 +151,11 @@ def batch_config(number, args, tri, workloads, torch, headline):
         dst.copy_(src)                      # reads and writes copy_calibration_mib MiB each
         torch.cuda.synchronize()
         del src, dst
-    # context beside the vendor's peak: what a plain streaming read of the same base vectors achieves here
+    # context beside the vendor's peak: what a bare streaming read of the same base vectors achieves here (best of a few
+    # launch shapes, plain or non-temporal loads)
     stream_gbs = tri.tri_stream_read_bandwidth(base_t, 3) if base_t.numel() * base_t.element_size() >= (1 << 20) else None
     if stream_gbs:
-        log(f"plain streaming read of the base ({base_t.numel() * base_t.element_size() / 1e9:.2f} GB): {stream_gbs:.0f} GB/s")
+        log(f"bare streaming read of the base ({base_t.numel() * base_t.element_size() / 1e9:.2f} GB): {stream_gbs:.0f} GB/s")
     # Settling, untimed and independent of --warmup: the first few hundred milliseconds under load run about
     # 7 % slower than the steady state (clocks ramping up), whatever is executed.
     log("settling 0.6 s under load")

@@ -416,9 +416,9 @@ int tri_pool_set_profiling(tri_pool *pool, uint32_t flags);
 int tri_pool_set_replay(tri_pool *pool, int on);
 
 /* Measurement helper (the paper's Sec. 2 roofline takes the memory bandwidth as given): the rate at which a
- * plain streaming-read kernel reads dev_buf [device] (bytes >= 1 MiB, 16-byte aligned; read-only) `repeats`
- * times in a row on hip_stream, timed with HIP events -- the achievable figure to quote beside the vendor's
- * peak.  dev_sink [device]: 4 writable bytes.  Synchronous. */
+ * bare streaming-read kernel reads dev_buf [device] (bytes >= 1 MiB, 16-byte aligned; read-only) `repeats`
+ * times in a row on hip_stream, timed with HIP events, the best of a few launch shapes with plain and with
+ * non-temporal loads -- the achievable figure to quote beside the vendor's peak.  dev_sink [device]: 4 writable bytes.  Synchronous. */
 int tri_stream_read_bandwidth(const void *dev_buf, size_t bytes, void *dev_sink, void *hip_stream, uint32_t repeats,
                               double *gb_per_s /*[host] out*/);
 
