@@ -17,7 +17,7 @@ TRI_OK, TRI_EINVAL, TRI_ENOMEM, TRI_EAGAIN, TRI_EHIP, TRI_ENOENT = 0, -1, -2, -3
 TRI_L2, TRI_IP = 0, 1
 TRI_F32, TRI_F16 = 0, 1
 TRI_CLASS_HIGH, TRI_CLASS_LOW = 0, 1
-TRI_FLAG_PROFILE, TRI_FLAG_KEEP_PROBES, TRI_FLAG_PROFILE_SCAN, TRI_FLAG_GRAPH = 1, 2, 4, 8
+TRI_FLAG_PROFILE, TRI_FLAG_KEEP_PROBES, TRI_FLAG_PROFILE_SCAN, TRI_FLAG_GRAPH, TRI_FLAG_STREAM_LISTS = 1, 2, 4, 8, 16
 TRI_ORDER_FIFO, TRI_ORDER_SLACK = 0, 1
 
 _HERE = os.path.dirname(os.path.abspath(__file__))

@@ -406,7 +406,7 @@ __device__ __forceinline__ void scan_lds_flush(ScanShared &sh, const ScanOut &ou
 // wavefront's blocks b = wave, wave+4, ... form ONE stream of (block, group) steps: while group g is
 // multiplied, the loads of the group SCAN_RING steps ahead -- in this block or the wavefront's next
 // one -- are already in flight, so the stream does not drain at block boundaries.
-template <int DT, int NG, bool FILTER>
+template <int DT, int NG, bool FILTER, bool NT>
 __device__ __forceinline__ void scan_tile_pipelined(const TriTile &tl, const uint8_t *__restrict__ qlds,
                                                     uint32_t pitch, ScanShared &sh, float *__restrict__ out_buf,
                                                     const ScanOut &out)
@@ -444,7 +444,7 @@ __device__ __forceinline__ void scan_tile_pipelined(const TriTile &tl, const uin
 #pragma unroll
     for (int s = 0; s < SCAN_RING; ++s) {
 #pragma unroll
-        for (int c = 0; c < 4; ++c) buf[s][c] = scan_ld16(vrs, off + s * 4096 + c * 1024);
+        for (int c = 0; c < 4; ++c) buf[s][c] = scan_ld16<NT>(vrs, off + s * 4096 + c * 1024);
         __builtin_amdgcn_sched_barrier(0);
     }
     for (uint32_t b = b0 + wave; b < nblocks; b += NWV) {
@@ -466,7 +466,7 @@ __device__ __forceinline__ void scan_tile_pipelined(const TriTile &tl, const uin
             const uint32_t nxt = g + SCAN_RING < NG ? off + (g + SCAN_RING) * 4096
                                                     : off_next + (g + SCAN_RING - NG) * 4096;
 #pragma unroll
-            for (int c = 0; c < 4; ++c) buf[s][c] = scan_ld16(vrs, nxt + c * 1024);
+            for (int c = 0; c < 4; ++c) buf[s][c] = scan_ld16<NT>(vrs, nxt + c * 1024);
             __builtin_amdgcn_sched_barrier(0);
         }
         off = off_next;
@@ -480,7 +480,7 @@ __device__ __forceinline__ void scan_tile_pipelined(const TriTile &tl, const uin
 
 // Any row length: same arithmetic, the groups of a block are loaded SCAN_RING at a time without
 // overlap across blocks.
-template <int DT, bool FILTER>
+template <int DT, bool FILTER, bool NT>
 __device__ __forceinline__ void scan_tile_generic(const TriTile &tl, const uint8_t *__restrict__ qlds, uint32_t pitch,
                                                   ScanShared &sh, float *__restrict__ out_buf, const ScanOut &out)
 {
@@ -523,7 +523,7 @@ __device__ __forceinline__ void scan_tile_generic(const TriTile &tl, const uint8
             for (int s = 0; s < SCAN_RING; ++s)
 #pragma unroll
                 for (int c = 0; c < 4; ++c)     // groups past the row end: offset forced out of range -> zeros
-                    buf[s][c] = scan_ld16(vrs, g0 + s < ngroups ? off + (g0 + s) * 4096 + c * 1024 : 0xFFFFFFF0u);
+                    buf[s][c] = scan_ld16<NT>(vrs, g0 + s < ngroups ? off + (g0 + s) * 4096 + c * 1024 : 0xFFFFFFF0u);
 #pragma unroll
             for (int s = 0; s < SCAN_RING; ++s) {
                 const uint32_t g = g0 + s < ngroups ? g0 + s : 0u;   // (zeros times any valid query piece)
@@ -541,7 +541,7 @@ __device__ __forceinline__ void scan_tile_generic(const TriTile &tl, const uint8
     }
 }
 
-template <int DT, int NG, bool FILTER>
+template <int DT, int NG, bool FILTER, bool NT>
 __global__ __launch_bounds__(TRI_SCAN_THREADS) __attribute__((amdgpu_waves_per_eu(2, 3))) void scan_lds_kernel(
     const TriTile *__restrict__ tiles, const uint32_t *__restrict__ n_tiles_ptr, uint32_t *__restrict__ tile_counter,
     uint32_t my_class, const uint32_t *__restrict__ sorted_slot, const uint8_t *__restrict__ slot_query,
@@ -587,9 +587,9 @@ __global__ __launch_bounds__(TRI_SCAN_THREADS) __attribute__((amdgpu_waves_per_e
         __syncthreads();
         const ScanOut out = {slot_cand_cnt, (uint2 *)out_buf, lstage, (uint32_t)tl.out_off};
         if constexpr (NG != 0)
-            scan_tile_pipelined<DT, NG, FILTER>(tl, qlds, pitch, sh, (float *)out_buf, out);
+            scan_tile_pipelined<DT, NG, FILTER, NT>(tl, qlds, pitch, sh, (float *)out_buf, out);
         else
-            scan_tile_generic<DT, FILTER>(tl, qlds, pitch, sh, (float *)out_buf, out);
+            scan_tile_generic<DT, FILTER, NT>(tl, qlds, pitch, sh, (float *)out_buf, out);
         if constexpr (FILTER) scan_lds_flush(sh, out, tl.nq);
     }
 }
@@ -609,13 +609,13 @@ template <bool FILTER, bool NT>
 static ScanVariant scan_variant_nt(uint32_t klass)
 {
     switch (klass) {
-    case 0: return {scan_lds_kernel<TRI_DT_F32, 0, FILTER>, false};
+    case 0: return {scan_lds_kernel<TRI_DT_F32, 0, FILTER, NT>, false};
     case 1: return {scan_wave_kernel<TRI_DT_F32, 4, 4, FILTER, NT>, true};
     case 2: return {scan_wave_kernel<TRI_DT_F32, 8, 4, FILTER, NT>, true};
-    case 3: return {scan_lds_kernel<TRI_DT_F32, 12, FILTER>, false};   // (the register-resident form spills for fp32 rows this
+    case 3: return {scan_lds_kernel<TRI_DT_F32, 12, FILTER, NT>, false};   // (the register-resident form spills for fp32 rows this
                                                                         //  wide, whatever the ring length: 150-350 bytes per lane)
-    case 4: return {scan_lds_kernel<TRI_DT_F32, 16, FILTER>, false};
-    case 5: return {scan_lds_kernel<TRI_DT_F16, 0, FILTER>, false};
+    case 4: return {scan_lds_kernel<TRI_DT_F32, 16, FILTER, NT>, false};
+    case 5: return {scan_lds_kernel<TRI_DT_F16, 0, FILTER, NT>, false};
     case 6: return {scan_wave_kernel<TRI_DT_F16, 4, 4, FILTER, NT>, true};
     case 7: return {scan_wave_kernel<TRI_DT_F16, 8, 4, FILTER, NT>, true};
     case 8: return {scan_wave_kernel<TRI_DT_F16, 12, 6, FILTER, NT>, true};
@@ -629,7 +629,7 @@ static ScanVariant scan_variant(uint32_t klass, bool nt = false)
     return nt ? scan_variant_nt<FILTER, true>(klass) : scan_variant_nt<FILTER, false>(klass);
 }
 
-static uint32_t g_scan_lds_limit[2 * TRI_SCAN_CLASSES] = {};
+static uint32_t g_scan_lds_limit[4 * TRI_SCAN_CLASSES] = {};     // [non-temporal][sample][class]
 
 // LDS of the workgroup kernels: the query tile at the widest attached row length; a kernel's limit is
 // raised (once per growth) before it is first launched with that much.
@@ -650,10 +650,12 @@ hipError_t tri_scan_prepare(uint32_t max_row_bytes, uint32_t class_mask)
 {
     for (uint32_t k = 0; k < TRI_SCAN_CLASSES; ++k) {
         if (!(class_mask & (1u << k))) continue;
-        for (int sample = 0; sample < 2; ++sample) {
-            const ScanVariant v = sample ? scan_variant<false>(k) : scan_variant<true>(k);
+        for (int var = 0; var < 4; ++var) {
+            const bool sample = var & 1, nt = var & 2;
+            const ScanVariant v = sample ? scan_variant<false>(k, nt) : scan_variant<true>(k, nt);
             if (v.wave) continue;
-            const hipError_t e = scan_raise_lds(v, (sample ? TRI_SCAN_CLASSES : 0) + k, scan_lds_bytes(max_row_bytes));
+            const hipError_t e = scan_raise_lds(v, (nt ? 2 * TRI_SCAN_CLASSES : 0) + (sample ? TRI_SCAN_CLASSES : 0) + k,
+                                                scan_lds_bytes(max_row_bytes));
             if (e != hipSuccess) return e;
         }
     }
@@ -681,7 +683,7 @@ hipError_t tri_launch_scan(const TriLaunchCtx &c, const TriDevWs &ws, uint32_t m
             const uint32_t lds = scan_lds_bytes(max_row_bytes);
             uint32_t per_cu = (160u * 1024u - 1024u) / (lds + 1024u + (sample ? 0u : SCAN_LSTAGE_CAP * 8u));
             per_cu = per_cu < 1 ? 1 : (per_cu > 3 ? 3 : per_cu);
-            const hipError_t e = scan_raise_lds(v, (sample ? TRI_SCAN_CLASSES : 0) + k, lds);
+            const hipError_t e = scan_raise_lds(v, (c.scan_nt ? 2 * TRI_SCAN_CLASSES : 0) + (sample ? TRI_SCAN_CLASSES : 0) + k, lds);
             if (e != hipSuccess) return e;
             hipLaunchKernelGGL(v.fn, dim3(c.n_cu * per_cu), dim3(TRI_SCAN_THREADS), lds, c.stream, tiles, n_ptr, counter,
                                k, ws.sorted_slot, ws.slot_query, c.slot_row_bytes, c.S, ws.slot_meta, ws.slot_qnorm,

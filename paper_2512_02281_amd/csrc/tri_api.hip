@@ -791,7 +791,7 @@ static void set_scan_nt(tri_pool *P)
     uint64_t bytes = 0;
     for (const tri_index *o : P->indexes)
         if (o) bytes += o->n * o->row_bytes;
-    P->ctx.scan_nt = bytes >= TRI_NT_INDEX_BYTES ? 1u : 0u;
+    P->ctx.scan_nt = (P->cfg.flags & TRI_FLAG_STREAM_LISTS) || bytes >= TRI_NT_INDEX_BYTES ? 1u : 0u;
 }
 
 extern "C" int ivf_build_tmp_bytes(const ivf_params *p, uint64_t n, int base_on_host, size_t *tmp_bytes)

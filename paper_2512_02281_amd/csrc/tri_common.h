@@ -215,7 +215,7 @@ struct TriDevWs {
 struct TriLaunchCtx {
     hipStream_t stream;
     uint32_t S, W, kmax, nprobe_max, max_total_lists, slot_row_bytes, n_cu;
-    uint32_t scan_nt;         // the one-wavefront scan kernels read the lists with non-temporal loads (see TRI_NT_INDEX_BYTES)
+    uint32_t scan_nt;         // the scan kernels read the lists with non-temporal loads (see TRI_NT_INDEX_BYTES)
 };
 
 // From this many bytes of attached vectors on, the lists are streamed past the caches (non-temporal loads): the

@@ -429,9 +429,11 @@ def test_every_row_length_class_and_long_lists(dtype, dim):
         ids, dist, n_out, probes, stats = harness.run_all(tri, pool, q)
         rep = harness.compare_with_oracle(oidx, base, queries, k, nprobe, metric, ids, dist, n_out, probes)
         _say(f"{dtype} d={dim}: parity {rep}")
-        # the same through three lists per step: thresholds then come from the running top-k as well
+        # the same through three lists per step: thresholds then come from the running top-k as well -- and with the
+        # lists read by non-temporal loads (the kernel variants a pool otherwise takes from 8 GB of vectors on)
         with harness.default_pool(tri, slots=16, items_per_step=48, lists_per_query_step=3, kmax=1024, nprobe_max=nlist,
-                                  max_dim=dim, max_nlist=nlist, max_total_lists=nlist, score_capacity=64 << 20) as pool2:
+                                  max_dim=dim, max_nlist=nlist, max_total_lists=nlist, score_capacity=64 << 20,
+                                  flags=tri.TRI_FLAG_KEEP_PROBES | tri.TRI_FLAG_STREAM_LISTS) as pool2:
             idx2 = pool2.build_index(base, dim, nlist, tdt, tri.TRI_L2, 4, centroids=centres)
             q2 = tri.make_queries(idx2, queries, k, nprobe, metric)
             ids2, dist2, n2, probes2, stats2 = harness.run_all(tri, pool2, q2)
