@@ -57,12 +57,13 @@ enum { TRI_FLAG_PROFILE = 1u,             /* bracket every stage of a step with 
        TRI_FLAG_PROFILE_SCAN = 4u,        /* bracket only the three launches of the list scan (four events): sample_ms,
                                              threshold_ms, scan_ms and the scan_* counters of tri_pool_kernel_times
                                              are filled, the other stage times stay zero                              */
-       TRI_FLAG_STREAM_LISTS = 16u,       /* read the inverted lists with non-temporal loads whatever the size of the
-                                             attached indexes.  Without the flag the pool does so once they hold 8 GB of
-                                             vectors or more (far more than the caches: the lists only pass through, and
-                                             keeping them out leaves the caches to the query rows); below that, the part
-                                             of a small index that the last-level cache serves from step to step is
-                                             worth more.  Results do not depend on it.                                */
+       TRI_FLAG_STREAM_LISTS = 16u,       /* read the inverted lists with non-temporal loads in every step.  Without
+                                             the flag the pool does so once the attached indexes hold 8 GB of vectors or
+                                             more (far more than the caches: the lists only pass through, and keeping
+                                             them out leaves the caches to the query rows), and then only in steps whose
+                                             lists are probed by 20 queries or fewer on average (a list probed by more
+                                             than 32 queries is read once per 32, the second time from the caches).
+                                             Results do not depend on it.                                             */
        TRI_FLAG_GRAPH = 8u };             /* Sec. 3.2 (fixed-shape step captured once, replayed): the launch sequence
                                              of a step is recorded as a HIP graph at three captured sizes (1/16, 1/4 and
                                              all of slots and items_per_step; once per size, step in flight and set of

@@ -60,8 +60,10 @@ typedef unsigned int scan_u32x4 __attribute__((ext_vector_type(4)));
 
 // 16 bytes of a list.  NT: the load is marked non-temporal -- for an index far larger than the last-level cache the
 // lists only pass through, and keeping them out of the caches leaves those to the query rows (configuration 4's
-// main launch: 5.74 -> 6.36 TB/s); for an index of a few GB, a tenth of which the cache still serves from step to
-// step, it costs that tenth.
+// main launch: 5.74 -> 6.36 TB/s).  It costs what the caches would have served: the part of a small index that stays
+// resident from step to step, and the second and later reads of a list that more than TRI_QT queries probe in one
+// step (one tile per TRI_QT queries: 16384 queries per step on the same index, 64 per list: 4.47 -> 5.41 ms).  Hence a
+// choice per launch (tri_scan_streams_lists).
 template <bool NT = false>
 __device__ __forceinline__ uint4 scan_ld16(__amdgpu_buffer_rsrc_t rs, uint32_t off)
 {
@@ -665,14 +667,14 @@ hipError_t tri_scan_prepare(uint32_t max_row_bytes, uint32_t class_mask)
 // Launch the scan kernels of one step -- the sample launch or the main launch -- one kernel per class
 // present in class_mask, each a persistent grid sized to what the chip holds at once.
 hipError_t tri_launch_scan(const TriLaunchCtx &c, const TriDevWs &ws, uint32_t max_row_bytes, uint32_t class_mask,
-                           bool sample)
+                           bool sample, bool nt)
 {
     const TriTile *tiles = sample ? ws.stiles : ws.tiles;
     const uint32_t *n_ptr = sample ? &ws.step_dev->n_sample_tiles : &ws.step_dev->n_tiles;
     void *out = sample ? (void *)ws.sample_scores : (void *)ws.cand;
     for (uint32_t k = 0; k < TRI_SCAN_CLASSES; ++k) {
         if (!(class_mask & (1u << k))) continue;
-        const ScanVariant v = sample ? scan_variant<false>(k, c.scan_nt != 0) : scan_variant<true>(k, c.scan_nt != 0);
+        const ScanVariant v = sample ? scan_variant<false>(k, nt) : scan_variant<true>(k, nt);
         uint32_t *counter = ws.tile_counter + (sample ? TRI_SCAN_CLASSES : 0) + k;
         if (v.wave) {
             // one wavefront per SIMD: 4 per compute unit
@@ -683,7 +685,7 @@ hipError_t tri_launch_scan(const TriLaunchCtx &c, const TriDevWs &ws, uint32_t m
             const uint32_t lds = scan_lds_bytes(max_row_bytes);
             uint32_t per_cu = (160u * 1024u - 1024u) / (lds + 1024u + (sample ? 0u : SCAN_LSTAGE_CAP * 8u));
             per_cu = per_cu < 1 ? 1 : (per_cu > 3 ? 3 : per_cu);
-            const hipError_t e = scan_raise_lds(v, (c.scan_nt ? 2 * TRI_SCAN_CLASSES : 0) + (sample ? TRI_SCAN_CLASSES : 0) + k, lds);
+            const hipError_t e = scan_raise_lds(v, (nt ? 2 * TRI_SCAN_CLASSES : 0) + (sample ? TRI_SCAN_CLASSES : 0) + k, lds);
             if (e != hipSuccess) return e;
             hipLaunchKernelGGL(v.fn, dim3(c.n_cu * per_cu), dim3(TRI_SCAN_THREADS), lds, c.stream, tiles, n_ptr, counter,
                                k, ws.sorted_slot, ws.slot_query, c.slot_row_bytes, c.S, ws.slot_meta, ws.slot_qnorm,

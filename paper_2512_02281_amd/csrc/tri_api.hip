@@ -114,8 +114,8 @@ struct StepRec {
     bool had_scan = false;
     // TRI_FLAG_GRAPH: the step's launch sequence with this entry's pinned blocks, recorded once per captured
     // size (and set of attached indexes) and replayed
-    hipGraph_t graph[N_SHAPES] = {};
-    hipGraphExec_t graph_exec[N_SHAPES] = {};
+    hipGraph_t graph[2 * N_SHAPES] = {};            // [lists streamed past the caches or not][captured size]
+    hipGraphExec_t graph_exec[2 * N_SHAPES] = {};
 };
 
 }  // namespace
@@ -791,7 +791,7 @@ static void set_scan_nt(tri_pool *P)
     uint64_t bytes = 0;
     for (const tri_index *o : P->indexes)
         if (o) bytes += o->n * o->row_bytes;
-    P->ctx.scan_nt = (P->cfg.flags & TRI_FLAG_STREAM_LISTS) || bytes >= TRI_NT_INDEX_BYTES ? 1u : 0u;
+    P->ctx.scan_nt = (P->cfg.flags & TRI_FLAG_STREAM_LISTS) ? 2u : bytes >= TRI_NT_INDEX_BYTES ? 1u : 0u;
 }
 
 extern "C" int ivf_build_tmp_bytes(const ivf_params *p, uint64_t n, int base_on_host, size_t *tmp_bytes)
@@ -1164,7 +1164,7 @@ void drop_graphs(tri_pool *P)
     (void)hipStreamSynchronize(P->stream);
     for (uint32_t i = 0; i < RING; ++i) {
         StepRec &R = P->ring[i];
-        for (uint32_t b = 0; b < N_SHAPES; ++b) {
+        for (uint32_t b = 0; b < 2 * N_SHAPES; ++b) {
             if (R.graph_exec[b]) (void)hipGraphExecDestroy(R.graph_exec[b]);
             if (R.graph[b]) (void)hipGraphDestroy(R.graph[b]);
             R.graph_exec[b] = nullptr;
@@ -1219,7 +1219,7 @@ StepShape step_shape(const tri_pool *P, uint32_t b)
 // form, every scan kernel variant the attached indexes need.  The kernels take what a step really holds
 // from its header, so one recording serves every later step that fits, until the set of attached
 // indexes changes.
-int record_step(tri_pool *P, StepRec &R, const TriDevWs &W, bool keep_probes, uint32_t b)
+int record_step(tri_pool *P, StepRec &R, const TriDevWs &W, bool keep_probes, uint32_t b, bool nt)
 {
     hipStream_t s = P->stream;
     uint32_t nlist_of[2] = {0, 0};
@@ -1241,9 +1241,9 @@ int record_step(tri_pool *P, StepRec &R, const TriDevWs &W, bool keep_probes, ui
         if (e == hipSuccess) e = tri_launch_coarse_select(P->ctx, P->ws, g, group_rows);
     }
     if (e == hipSuccess) e = tri_launch_pack(P->ctx, W, sh.items, P->total_lists, P->n_order);
-    if (e == hipSuccess) e = tri_launch_scan(P->ctx, P->ws, P->attached_row_bytes, P->scan_class_mask, true);
+    if (e == hipSuccess) e = tri_launch_scan(P->ctx, P->ws, P->attached_row_bytes, P->scan_class_mask, true, nt);
     if (e == hipSuccess) e = tri_launch_threshold(P->ctx, P->ws, sh.slots);
-    if (e == hipSuccess) e = tri_launch_scan(P->ctx, P->ws, P->attached_row_bytes, P->scan_class_mask, false);
+    if (e == hipSuccess) e = tri_launch_scan(P->ctx, P->ws, P->attached_row_bytes, P->scan_class_mask, false, nt);
     if (e == hipSuccess) e = tri_launch_merge(P->ctx, W, sh.slots, keep_probes);
     hipGraph_t g = nullptr;
     const hipError_t e2 = hipStreamEndCapture(s, &g);      // (always: a stream must not be left capturing)
@@ -1257,8 +1257,8 @@ int record_step(tri_pool *P, StepRec &R, const TriDevWs &W, bool keep_probes, ui
         (void)hipGraphDestroy(g);
         return tri_fail(TRI_EHIP, "hipGraphInstantiate -> %s", hipGetErrorString(e));
     }
-    R.graph[b] = g;
-    R.graph_exec[b] = x;
+    R.graph[b + (nt ? N_SHAPES : 0)] = g;
+    R.graph_exec[b + (nt ? N_SHAPES : 0)] = x;
     return TRI_OK;
 }
 
@@ -1486,6 +1486,7 @@ int step_locked(tri_pool *P, tri_step_stats *st)
     W.res_block = (uint32_t *)R.down_dev;
     W.res_probes = (uint32_t *)(R.down_dev + P->down_probe_off);
     const bool keep_probes = (cfg.flags & TRI_FLAG_KEEP_PROBES) != 0;
+    const bool nt = tri_scan_streams_lists(P->ctx.scan_nt, n_items, P->total_lists);   // (lists read past the caches in this step?)
     if (replay) {
         // Sec. 3.2: the step's launch sequence, recorded once at its fixed, largest shape, is replayed; what
         // this step holds stands in the header the first kernel pulls.
@@ -1494,11 +1495,12 @@ int step_locked(tri_pool *P, tri_step_stats *st)
             const StepShape sh = step_shape(P, b);
             if (n_new <= sh.slots && n_plan <= sh.slots && n_items <= sh.items && n_groups <= sh.groups) break;
         }
-        if (!R.graph_exec[b]) {
-            rc = record_step(P, R, W, keep_probes, b);
+        const uint32_t gi = b + (nt ? N_SHAPES : 0);
+        if (!R.graph_exec[gi]) {
+            rc = record_step(P, R, W, keep_probes, b, nt);
             if (rc) return rc;
         }
-        HIP_TRY(hipGraphLaunch(R.graph_exec[b], s));
+        HIP_TRY(hipGraphLaunch(R.graph_exec[gi], s));
     } else {
         W.step_host = prof || prof_scan ? (TriStepDev *)(R.down_dev + P->down_step_off) : nullptr;
         HIP_TRY(tri_launch_pull_block(s, P->ws.upload, R.up_dev, up_bytes));
@@ -1514,11 +1516,11 @@ int step_locked(tri_pool *P, tri_step_stats *st)
         HIP_TRY(tri_launch_pack(P->ctx, W, n_items, P->total_lists, P->n_order));
         if (prof || (prof_scan && n_items)) HIP_TRY(hipEventRecord(R.ev[3], s));
         // thresholds: score a sample of every probed list, k-th best of each slot's sample
-        if (n_items) HIP_TRY(tri_launch_scan(P->ctx, P->ws, P->attached_row_bytes, P->scan_class_mask, true));
+        if (n_items) HIP_TRY(tri_launch_scan(P->ctx, P->ws, P->attached_row_bytes, P->scan_class_mask, true, nt));
         if (prof || (prof_scan && n_items)) HIP_TRY(hipEventRecord(R.ev[4], s));
         if (n_items) HIP_TRY(tri_launch_threshold(P->ctx, P->ws, n_plan));
         if (prof || (prof_scan && n_items)) HIP_TRY(hipEventRecord(R.ev[5], s));
-        if (n_items) HIP_TRY(tri_launch_scan(P->ctx, P->ws, P->attached_row_bytes, P->scan_class_mask, false));
+        if (n_items) HIP_TRY(tri_launch_scan(P->ctx, P->ws, P->attached_row_bytes, P->scan_class_mask, false, nt));
         if (prof || (prof_scan && n_items)) HIP_TRY(hipEventRecord(R.ev[6], s));
         HIP_TRY(tri_launch_merge(P->ctx, W, n_plan, keep_probes));
         if (prof) HIP_TRY(hipEventRecord(R.ev[7], s));

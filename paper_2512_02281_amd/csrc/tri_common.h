@@ -215,13 +215,21 @@ struct TriDevWs {
 struct TriLaunchCtx {
     hipStream_t stream;
     uint32_t S, W, kmax, nprobe_max, max_total_lists, slot_row_bytes, n_cu;
-    uint32_t scan_nt;         // the scan kernels read the lists with non-temporal loads (see TRI_NT_INDEX_BYTES)
+    uint32_t scan_nt;         // 0: the scan kernels may not read the lists with non-temporal loads; 1: they may (the attached
+                              // indexes are large, TRI_NT_INDEX_BYTES); 2: they must (TRI_FLAG_STREAM_LISTS)
 };
 
 // From this many bytes of attached vectors on, the lists are streamed past the caches (non-temporal loads): the
 // last-level cache (256 MB) then holds a few per cent of them at best.  Measured: +9 % on the scan of a 15 GB index,
 // -10 % on that of a 3 GB index.
 #define TRI_NT_INDEX_BYTES (8ull << 30)
+// ... and only in a step whose lists are mostly read once: a list probed by more than TRI_QT queries is read once per
+// tile of TRI_QT queries, the second time from the caches -- unless the first read went past them.  Measured on the
+// 15 GB index: 16 queries per list on average +9 %, 64 per list -21 %; on a 3 GB index with 32 per list -10 %.
+inline bool tri_scan_streams_lists(uint32_t scan_nt, uint32_t n_items, uint32_t total_lists)
+{
+    return scan_nt == 2u || (scan_nt == 1u && (uint64_t)n_items <= 20ull * total_lists);
+}
 
 // What another engine of the library needs to know of a resident index (tri_api.hip owns the object).
 struct tri_index;
@@ -266,7 +274,7 @@ hipError_t tri_launch_coarse_select(const TriLaunchCtx &c, const TriDevWs &ws, u
 hipError_t tri_launch_pack(const TriLaunchCtx &c, const TriDevWs &ws, uint32_t grid_items, uint32_t total_lists,
                            uint32_t n_order);
 hipError_t tri_launch_scan(const TriLaunchCtx &c, const TriDevWs &ws, uint32_t max_row_bytes, uint32_t class_mask,
-                           bool sample);
+                           bool sample, bool nt);
 hipError_t tri_launch_threshold(const TriLaunchCtx &c, const TriDevWs &ws, uint32_t grid_plan);
 // one-time set-up the launchers above would otherwise do at their first launch (LDS limits)
 hipError_t tri_scan_prepare(uint32_t max_row_bytes, uint32_t class_mask);
