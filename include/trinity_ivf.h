@@ -58,10 +58,10 @@ enum { TRI_FLAG_PROFILE = 1u,             /* bracket every stage of a step with 
                                              threshold_ms, scan_ms and the scan_* counters of tri_pool_kernel_times
                                              are filled, the other stage times stay zero                              */
        TRI_FLAG_STREAM_LISTS = 16u,       /* read the inverted lists with non-temporal loads in every step.  Without
-                                             the flag the pool does so once the attached indexes hold 8 GB of vectors or
-                                             more (far more than the caches: the lists only pass through, and keeping
+                                             the flag the pool does so once the attached indexes hold 1 GB of vectors or
+                                             more (several times the caches: the lists only pass through, and keeping
                                              them out leaves the caches to the query rows), and then only in steps whose
-                                             lists are probed by 20 queries or fewer on average (a list probed by more
+                                             lists are probed by 24 queries or fewer on average (a list probed by more
                                              than 32 queries is read once per 32, the second time from the caches).
                                              Results do not depend on it.                                             */
        TRI_FLAG_GRAPH = 8u };             /* Sec. 3.2 (fixed-shape step captured once, replayed): the launch sequence

@@ -219,16 +219,16 @@ struct TriLaunchCtx {
                               // indexes are large, TRI_NT_INDEX_BYTES); 2: they must (TRI_FLAG_STREAM_LISTS)
 };
 
-// From this many bytes of attached vectors on, the lists are streamed past the caches (non-temporal loads): the
-// last-level cache (256 MB) then holds a few per cent of them at best.  Measured: +9 % on the scan of a 15 GB index,
-// -10 % on that of a 3 GB index.
-#define TRI_NT_INDEX_BYTES (8ull << 30)
+// From this many bytes of attached vectors on (several times the 256 MB last-level cache), the lists may be streamed
+// past the caches (non-temporal loads) ...
+#define TRI_NT_INDEX_BYTES (1ull << 30)
 // ... and only in a step whose lists are mostly read once: a list probed by more than TRI_QT queries is read once per
 // tile of TRI_QT queries, the second time from the caches -- unless the first read went past them.  Measured on the
-// 15 GB index: 16 queries per list on average +9 %, 64 per list -21 %; on a 3 GB index with 32 per list -10 %.
+// 15 GB index: 16 queries per list on average +9 %, 64 per list -21 %; on a 3 GB index with 32 per list -10 %; on a
+// 1.5 GB index with 24 per list +5 %, and +3.5 % on the two-index stream of configuration 3 (8 lists per query and step).
 inline bool tri_scan_streams_lists(uint32_t scan_nt, uint32_t n_items, uint32_t total_lists)
 {
-    return scan_nt == 2u || (scan_nt == 1u && (uint64_t)n_items <= 20ull * total_lists);
+    return scan_nt == 2u || (scan_nt == 1u && (uint64_t)n_items <= 24ull * total_lists);
 }
 
 // What another engine of the library needs to know of a resident index (tri_api.hip owns the object).
