@@ -1536,29 +1536,43 @@ __global__ __launch_bounds__(TRI_SEL_THREADS) __attribute__((amdgpu_waves_per_eu
         for (int j = 0; j < 4; ++j) k[j] = sel_key(__uint_as_float(raw[j]), d.metric) | (e0 + j < nlist ? 0u : 0xFFFFFFFFu);
     };
     const uint32_t nchunks = (nlist + 2047u) / 2048u;                 // (uniform)
-    uint32_t m[CW_CHUNKS];                                            // minimum of line c * 64 + (l % 8) * 8 + l / 8
-    // (the loads of chunk c + 1 are issued before chunk c is worked on; a chunk past the row's end costs no memory
-    // access and is skipped)
+    // A row of at most 2048 scores is one chunk, which stays in registers: the minima are then taken over the four
+    // scores of every load and lane (up to 512 of them -- the lines of so short a row would be too few to bound
+    // anything), and pass 2 needs no second read.
+    const bool short_row = nchunks == 1;
+    uint32_t m[CW_CHUNKS];        // long rows: minimum of line c * 64 + (l % 8) * 8 + l / 8; short rows: of this lane's load c
     cw_u32x4 v[2][8];
 #pragma unroll
     for (int q = 0; q < 8; ++q) v[0][q] = __builtin_amdgcn_raw_buffer_load_b128(rrs, lane * 16u, q * 1024u, 2);   // (read once: non-temporal)
+    if (short_row) {
 #pragma unroll
-    for (int c = 0; c < CW_CHUNKS; ++c) {
-        if (c + 1 < CW_CHUNKS) {
-#pragma unroll
-            for (int q = 0; q < 8; ++q)
-                v[(c + 1) & 1][q] = __builtin_amdgcn_raw_buffer_load_b128(rrs, lane * 16u, (c + 1) * 8192u + q * 1024u, 2);
+        for (int q = 0; q < 8; ++q) {
+            uint32_t k[4];
+            keys_of(v[0][q], q * 256u + lane * 4u, k);
+            const uint32_t mn = k[0] < k[1] ? k[0] : k[1], mn2 = k[2] < k[3] ? k[2] : k[3];
+            m[q] = mn < mn2 ? mn : mn2;
         }
-        m[c] = 0xFFFFFFFFu;
-        if ((uint32_t)c < nchunks) {
+    } else {
+        // (the loads of chunk c + 1 are issued before chunk c is worked on; a chunk past the row's end costs no memory
+        // access and is skipped)
 #pragma unroll
-            for (int q = 0; q < 8; ++q) {
-                uint32_t k[4];
-                keys_of(v[c & 1][q], c * 2048u + q * 256u + lane * 4u, k);
-                uint32_t mn = k[0] < k[1] ? k[0] : k[1];
-                const uint32_t mn2 = k[2] < k[3] ? k[2] : k[3];
-                mn = cw_min8(mn < mn2 ? mn : mn2);
-                m[c] = (lane & 7u) == (uint32_t)q ? mn : m[c];
+        for (int c = 0; c < CW_CHUNKS; ++c) {
+            if (c + 1 < CW_CHUNKS) {
+#pragma unroll
+                for (int q = 0; q < 8; ++q)
+                    v[(c + 1) & 1][q] = __builtin_amdgcn_raw_buffer_load_b128(rrs, lane * 16u, (c + 1) * 8192u + q * 1024u, 2);
+            }
+            m[c] = 0xFFFFFFFFu;
+            if ((uint32_t)c < nchunks) {
+#pragma unroll
+                for (int q = 0; q < 8; ++q) {
+                    uint32_t k[4];
+                    keys_of(v[c & 1][q], c * 2048u + q * 256u + lane * 4u, k);
+                    uint32_t mn = k[0] < k[1] ? k[0] : k[1];
+                    const uint32_t mn2 = k[2] < k[3] ? k[2] : k[3];
+                    mn = cw_min8(mn < mn2 ? mn : mn2);
+                    m[c] = (lane & 7u) == (uint32_t)q ? mn : m[c];
+                }
             }
         }
     }
@@ -1571,6 +1585,31 @@ __global__ __launch_bounds__(TRI_SEL_THREADS) __attribute__((amdgpu_waves_per_eu
         if (cnt < d.nprobe) T |= 1u << b;
     }
     if (T == 0xFFFFFFFFu) { defer(); return; }                        // (fewer than nprobe minima that are not padding)
+    if (short_row) {
+        uint32_t cnt = 0;                                             // (the keys are made twice rather than kept: registers)
+#pragma unroll
+        for (int q = 0; q < 8; ++q) {
+            uint32_t k[4];
+            keys_of(v[0][q], q * 256u + lane * 4u, k);
+#pragma unroll
+            for (int j = 0; j < 4; ++j) cnt += k[j] <= T ? 1u : 0u;
+        }
+        const uint32_t inc2 = thr_wave_scan(cnt, 0u, [](uint32_t a, uint32_t b2) { return a + b2; });
+        const uint32_t total = (uint32_t)__builtin_amdgcn_readlane((int)inc2, 63);
+        if (total > MRG_CAP) { defer(); return; }
+        uint32_t pos = inc2 - cnt;
+#pragma unroll
+        for (int q = 0; q < 8; ++q) {
+            uint32_t k[4];
+            keys_of(v[0][q], q * 256u + lane * 4u, k);
+#pragma unroll
+            for (int j = 0; j < 4; ++j)
+                if (k[j] <= T) L.a[pos++] = ((uint64_t)k[j] << 32) | (q * 256u + lane * 4u + j);
+        }
+        mrg_rank_sort(L.a, total, L.b, lane);
+        for (uint32_t i = lane; i < d.nprobe; i += 64) dst[i] = (uint32_t)(L.b[i] & 0xFFFFFFFFu);
+        return;
+    }
     // the lines to read again
     uint32_t mine = 0;
 #pragma unroll
