@@ -462,7 +462,10 @@ def test_recorded_step_replays_match_kernel_by_kernel_launches():
         scratch.add_(1.0)
         torch.cuda.synchronize()
 
-    for name, flags in [("eager", tri.TRI_FLAG_KEEP_PROBES), ("graph", tri.TRI_FLAG_KEEP_PROBES | tri.TRI_FLAG_GRAPH)]:
+    # (the recorded pool also reads its lists with non-temporal loads: recordings are kept per such choice, and the
+    # results must not depend on it)
+    for name, flags in [("eager", tri.TRI_FLAG_KEEP_PROBES),
+                        ("graph", tri.TRI_FLAG_KEEP_PROBES | tri.TRI_FLAG_GRAPH | tri.TRI_FLAG_STREAM_LISTS)]:
         _say(f"recorded step: {name}")
         with harness.default_pool(tri, slots=24, max_dim=768, max_outstanding=512, lists_per_query_step=4,
                                   flags=flags) as pool:
