@@ -1087,12 +1087,32 @@ __global__ __launch_bounds__(TRI_SEL_THREADS) __attribute__((amdgpu_waves_per_eu
     {
         const bool all = thr == 0xFFFFFFFFu;
         const float edge = tri_key_score(thr, 0u);
-        for (uint32_t s = from_memory; s < e.take; ++s) {
-            const uint32_t it = e.item_base + s, g = item_glist[it];
-            const uint32_t len = min(glist_len[g], (uint32_t)TRI_SAMPLE_VECS), voff = glist_voff[g];
-            float val = lane < len ? sample_scores[(size_t)item_sorted_pos[it] * TRI_SAMPLE_VECS + lane] : pad;
-            if (desc) val = -val;
-            emit(lane < len && (all || val <= edge), val, voff);
+        // (64 items a round: every lane fetches what describes one of them, then the items' sample rows are read four at
+        // a time -- one dependent load per item instead of three, and four of those in flight)
+        for (uint32_t s0 = from_memory; s0 < e.take; s0 += 64) {
+            const bool mine = s0 + lane < e.take;
+            const uint32_t it = e.item_base + s0 + lane, g = mine ? item_glist[it] : 0u;
+            const uint32_t len_l = mine ? min(glist_len[g], (uint32_t)TRI_SAMPLE_VECS) : 0u;
+            const uint32_t voff_l = mine ? glist_voff[g] : 0u, row_l = mine ? item_sorted_pos[it] : 0u;
+            const uint32_t n = min(64u, e.take - s0);
+            for (uint32_t j = 0; j < n; j += 4) {
+                float val[4];
+                uint32_t len4[4], voff4[4];
+#pragma unroll
+                for (int u = 0; u < 4; ++u) {
+                    const uint32_t jj = j + u < n ? j + u : n - 1;                     // (uniform)
+                    len4[u] = (uint32_t)__builtin_amdgcn_readlane((int)len_l, (int)jj);
+                    voff4[u] = (uint32_t)__builtin_amdgcn_readlane((int)voff_l, (int)jj);
+                    const uint32_t row = (uint32_t)__builtin_amdgcn_readlane((int)row_l, (int)jj);
+                    val[u] = lane < len4[u] ? sample_scores[(size_t)row * TRI_SAMPLE_VECS + lane] : pad;
+                }
+#pragma unroll
+                for (int u = 0; u < 4; ++u) {
+                    if (j + u >= n) break;                                              // (uniform)
+                    const float x = desc ? -val[u] : val[u];
+                    emit(lane < len4[u] && (all || x <= edge), x, voff4[u]);
+                }
+            }
         }
     }
     if (lane == 0) {
