@@ -1521,7 +1521,10 @@ __device__ __forceinline__ uint32_t cw_min8(uint32_t v)
     return o < v ? o : v;
 }
 
-__global__ __launch_bounds__(TRI_SEL_THREADS) __attribute__((amdgpu_waves_per_eu(4, 4))) void coarse_select_wave_kernel(
+// SHORT: the instantiation for rows of at most 4096 scores (kept in registers); the other one serves the longer rows.
+// A launch of the wrong one for a group's index leaves at once.
+template <bool SHORT>
+__global__ __launch_bounds__(TRI_SEL_THREADS) __attribute__((amdgpu_waves_per_eu(SHORT ? 3 : 4, SHORT ? 3 : 4))) void coarse_select_wave_kernel(
     const float *__restrict__ scores, const uint8_t *__restrict__ upload, uint32_t gi,
     const TriIndexDev *__restrict__ indexes, uint32_t *__restrict__ probe, uint32_t nprobe_max,
     uint32_t *__restrict__ counters, uint32_t *__restrict__ queue)
@@ -1538,6 +1541,7 @@ __global__ __launch_bounds__(TRI_SEL_THREADS) __attribute__((amdgpu_waves_per_eu
     const uint32_t r = blockIdx.x * NW + wave;
     if (r >= g.m) return;
     const uint32_t nlist = indexes[g.index].nlist, ldc = tri_coarse_ldc(nlist);
+    if ((nlist <= 4096u) != SHORT) return;
     const TriNewDesc d = ((const TriNewDesc *)(upload + hdr->desc_off))[g.first_new + r];
     uint32_t *dst = probe + (size_t)d.slot * nprobe_max;
     CoarseWaveLds &L = wv[wave];
@@ -1556,22 +1560,31 @@ __global__ __launch_bounds__(TRI_SEL_THREADS) __attribute__((amdgpu_waves_per_eu
         for (int j = 0; j < 4; ++j) k[j] = sel_key(__uint_as_float(raw[j]), d.metric) | (e0 + j < nlist ? 0u : 0xFFFFFFFFu);
     };
     const uint32_t nchunks = (nlist + 2047u) / 2048u;                 // (uniform)
-    // A row of at most 2048 scores is one chunk, which stays in registers: the minima are then taken over the four
-    // scores of every load and lane (up to 512 of them -- the lines of so short a row would be too few to bound
+    // A row of at most 4096 scores is one or two chunks, which stay in registers: the minima are then taken over the
+    // four scores of every load and lane (up to 1024 of them -- the lines of so short a row would be too few to bound
     // anything), and pass 2 needs no second read.
-    const bool short_row = nchunks == 1;
-    uint32_t m[CW_CHUNKS];        // long rows: minimum of line c * 64 + (l % 8) * 8 + l / 8; short rows: of this lane's load c
+    constexpr bool short_row = SHORT;                                 // (nchunks <= 2)
+    constexpr int CW_MINIMA = SHORT ? 16 : CW_CHUNKS;
+    uint32_t m[CW_MINIMA];        // long rows: m[c] = minimum of line c * 64 + (l % 8) * 8 + l / 8; short rows: m[8 c + q] = of this lane's load q of chunk c
+    if constexpr (SHORT) {
+#pragma unroll
+        for (int i = 0; i < CW_MINIMA; ++i) m[i] = 0xFFFFFFFFu;
+    }
     cw_u32x4 v[2][8];
 #pragma unroll
     for (int q = 0; q < 8; ++q) v[0][q] = __builtin_amdgcn_raw_buffer_load_b128(rrs, lane * 16u, q * 1024u, 2);   // (read once: non-temporal)
-    if (short_row) {
+    if constexpr (short_row) {
 #pragma unroll
-        for (int q = 0; q < 8; ++q) {
-            uint32_t k[4];
-            keys_of(v[0][q], q * 256u + lane * 4u, k);
-            const uint32_t mn = k[0] < k[1] ? k[0] : k[1], mn2 = k[2] < k[3] ? k[2] : k[3];
-            m[q] = mn < mn2 ? mn : mn2;
-        }
+        for (int q = 0; q < 8; ++q) v[1][q] = __builtin_amdgcn_raw_buffer_load_b128(rrs, lane * 16u, 8192u + q * 1024u, 2);
+#pragma unroll
+        for (int c = 0; c < 2; ++c)
+#pragma unroll
+            for (int q = 0; q < 8; ++q) {
+                uint32_t k[4];
+                keys_of(v[c][q], c * 2048u + q * 256u + lane * 4u, k);
+                const uint32_t mn = k[0] < k[1] ? k[0] : k[1], mn2 = k[2] < k[3] ? k[2] : k[3];
+                m[c * 8 + q] = mn < mn2 ? mn : mn2;
+            }
     } else {
         // (the loads of chunk c + 1 are issued before chunk c is worked on; a chunk past the row's end costs no memory
         // access and is skipped)
@@ -1601,31 +1614,36 @@ __global__ __launch_bounds__(TRI_SEL_THREADS) __attribute__((amdgpu_waves_per_eu
         const uint32_t trial = T | ((1u << b) - 1u);                  // (bit b clear, every lower bit set)
         uint32_t cnt = 0;
 #pragma unroll
-        for (int c = 0; c < CW_CHUNKS; ++c) cnt += (uint32_t)__popcll(__ballot(m[c] <= trial));
+        for (int c = 0; c < CW_MINIMA; ++c)
+            cnt += (uint32_t)__popcll(__ballot(m[c] <= trial));
         if (cnt < d.nprobe) T |= 1u << b;
     }
     if (T == 0xFFFFFFFFu) { defer(); return; }                        // (fewer than nprobe minima that are not padding)
-    if (short_row) {
+    if constexpr (short_row) {
         uint32_t cnt = 0;                                             // (the keys are made twice rather than kept: registers)
 #pragma unroll
-        for (int q = 0; q < 8; ++q) {
-            uint32_t k[4];
-            keys_of(v[0][q], q * 256u + lane * 4u, k);
+        for (int c = 0; c < 2; ++c)
 #pragma unroll
-            for (int j = 0; j < 4; ++j) cnt += k[j] <= T ? 1u : 0u;
-        }
+            for (int q = 0; q < 8; ++q) {
+                uint32_t k[4];
+                keys_of(v[c][q], c * 2048u + q * 256u + lane * 4u, k);
+#pragma unroll
+                for (int j = 0; j < 4; ++j) cnt += k[j] <= T ? 1u : 0u;
+            }
         const uint32_t inc2 = thr_wave_scan(cnt, 0u, [](uint32_t a, uint32_t b2) { return a + b2; });
         const uint32_t total = (uint32_t)__builtin_amdgcn_readlane((int)inc2, 63);
         if (total > MRG_CAP) { defer(); return; }
         uint32_t pos = inc2 - cnt;
 #pragma unroll
-        for (int q = 0; q < 8; ++q) {
-            uint32_t k[4];
-            keys_of(v[0][q], q * 256u + lane * 4u, k);
+        for (int c = 0; c < 2; ++c)
 #pragma unroll
-            for (int j = 0; j < 4; ++j)
-                if (k[j] <= T) L.a[pos++] = ((uint64_t)k[j] << 32) | (q * 256u + lane * 4u + j);
-        }
+            for (int q = 0; q < 8; ++q) {
+                uint32_t k[4];
+                keys_of(v[c][q], c * 2048u + q * 256u + lane * 4u, k);
+#pragma unroll
+                for (int j = 0; j < 4; ++j)
+                    if (k[j] <= T) L.a[pos++] = ((uint64_t)k[j] << 32) | (c * 2048u + q * 256u + lane * 4u + j);
+            }
         mrg_rank_sort(L.a, total, L.b, lane);
         for (uint32_t i = lane; i < d.nprobe; i += 64) dst[i] = (uint32_t)(L.b[i] & 0xFFFFFFFFu);
         return;
@@ -1694,12 +1712,18 @@ __global__ __launch_bounds__(TRI_SEL_THREADS) void coarse_select_kernel(
     }
 }
 
-hipError_t tri_launch_coarse_select(const TriLaunchCtx &c, const TriDevWs &ws, uint32_t group, uint32_t grid_m)
+// nlist: the number of centroids of the group's index when the caller knows it (only the kernel for that row length is
+// launched), 0 when it does not (a recorded step serves whatever index a group turns out to have: both are).
+hipError_t tri_launch_coarse_select(const TriLaunchCtx &c, const TriDevWs &ws, uint32_t group, uint32_t grid_m, uint32_t nlist)
 {
     if (grid_m == 0) return hipSuccess;
     constexpr uint32_t NW = TRI_SEL_THREADS / 64;
-    hipLaunchKernelGGL(coarse_select_wave_kernel, dim3((grid_m + NW - 1) / NW), dim3(TRI_SEL_THREADS), 0, c.stream,
-                       ws.coarse_scores, ws.upload, group, ws.indexes, ws.probe, c.nprobe_max, ws.rescans, ws.coarse_queue);
+    if (nlist == 0 || nlist <= 4096u)
+        hipLaunchKernelGGL(coarse_select_wave_kernel<true>, dim3((grid_m + NW - 1) / NW), dim3(TRI_SEL_THREADS), 0, c.stream,
+                           ws.coarse_scores, ws.upload, group, ws.indexes, ws.probe, c.nprobe_max, ws.rescans, ws.coarse_queue);
+    if (nlist == 0 || nlist > 4096u)
+        hipLaunchKernelGGL(coarse_select_wave_kernel<false>, dim3((grid_m + NW - 1) / NW), dim3(TRI_SEL_THREADS), 0, c.stream,
+                           ws.coarse_scores, ws.upload, group, ws.indexes, ws.probe, c.nprobe_max, ws.rescans, ws.coarse_queue);
     hipLaunchKernelGGL(coarse_select_kernel, dim3(grid_m < 256u ? grid_m : 256u), dim3(TRI_SEL_THREADS), 0, c.stream,
                        ws.coarse_scores, ws.upload, group, ws.indexes, ws.probe, c.nprobe_max, ws.rescans, ws.coarse_queue);
     return hipGetLastError();

@@ -1238,7 +1238,7 @@ int record_step(tri_pool *P, StepRec &R, const TriDevWs &W, bool keep_probes, ui
     for (uint32_t g = 0; g < sh.groups && e == hipSuccess; ++g) {
         for (int dt = 0; dt < 2 && e == hipSuccess; ++dt)
             if (nlist_of[dt]) e = tri_launch_coarse_gemm_step(P->ctx, P->ws, dt ? TRI_F16 : TRI_F32, g, group_rows, nlist_of[dt]);
-        if (e == hipSuccess) e = tri_launch_coarse_select(P->ctx, P->ws, g, group_rows);
+        if (e == hipSuccess) e = tri_launch_coarse_select(P->ctx, P->ws, g, group_rows, 0u);
     }
     if (e == hipSuccess) e = tri_launch_pack(P->ctx, W, sh.items, P->total_lists, P->n_order);
     if (e == hipSuccess) e = tri_launch_scan(P->ctx, P->ws, P->attached_row_bytes, P->scan_class_mask, true, nt);
@@ -1510,7 +1510,7 @@ int step_locked(tri_pool *P, tri_step_stats *st)
         for (uint32_t g = 0; g < n_groups; ++g) {
             const tri_index *ix = P->indexes[hdr_h->group[g].index];
             HIP_TRY(tri_launch_coarse_gemm_step(P->ctx, P->ws, (int)ix->p.dtype, g, hdr_h->group[g].m, ix->p.nlist));
-            HIP_TRY(tri_launch_coarse_select(P->ctx, P->ws, g, hdr_h->group[g].m));
+            HIP_TRY(tri_launch_coarse_select(P->ctx, P->ws, g, hdr_h->group[g].m, ix->p.nlist));
         }
         if (prof) HIP_TRY(hipEventRecord(R.ev[2], s));
         HIP_TRY(tri_launch_pack(P->ctx, W, n_items, P->total_lists, P->n_order));

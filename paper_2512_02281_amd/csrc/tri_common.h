@@ -270,7 +270,7 @@ hipError_t tri_launch_coarse_gemm(hipStream_t s, int dtype, const void *a_rows, 
 // into ws.coarse_scores with a row pitch of nlist rounded up to 32; dtype = the kernel variant to launch
 hipError_t tri_launch_coarse_gemm_step(const TriLaunchCtx &c, const TriDevWs &ws, int dtype, uint32_t group,
                                        uint32_t grid_m, uint32_t grid_n);
-hipError_t tri_launch_coarse_select(const TriLaunchCtx &c, const TriDevWs &ws, uint32_t group, uint32_t grid_m);
+hipError_t tri_launch_coarse_select(const TriLaunchCtx &c, const TriDevWs &ws, uint32_t group, uint32_t grid_m, uint32_t nlist);
 hipError_t tri_launch_pack(const TriLaunchCtx &c, const TriDevWs &ws, uint32_t grid_items, uint32_t total_lists,
                            uint32_t n_order);
 hipError_t tri_launch_scan(const TriLaunchCtx &c, const TriDevWs &ws, uint32_t max_row_bytes, uint32_t class_mask,
