@@ -71,19 +71,23 @@ __device__ __forceinline__ void coarse_gemm_tile(
     // (fetches past the last stage are harmless: inside the matrix they read bytes that are never
     // multiplied, past its end zeros -- and being unconditional they keep the count of loads in flight
     // known at every wait, so depositing one stage never waits for the loads of the next)
+    // metric of the tile's rows, for the epilogue.  Asked for before the first fetch and stored with the first stage:
+    // waiting for it later would wait for every fetch issued before it, and the loop would be entered with no load
+    // outstanding -- from which the compiler concludes (the loop's waits must hold on every path into it) that the
+    // deposits inside the loop have to wait for ALL outstanding loads, the set fetched one stage ago included, which
+    // halves the distance the fetches run ahead.
+    uint32_t *row_is_ip = (uint32_t *)(cg_lds + CG_LDS);
+    const uint32_t ml0 = tid < a_rows ? tid : a_rows - 1;
+    const uint32_t my_metric = row_metric ? row_metric[(size_t)(bm + ml0) * metric_stride] : fixed_metric;
+    asm volatile("" ::: "memory");
     fetch(r0, 0);
     deposit(r0, 0);
+    row_is_ip[tid] = my_metric;
     asm volatile("" ::: "memory");          // (the issue order of the two sets must be the loop's: older set first)
     fetch(r1, 1);
     asm volatile("" ::: "memory");
     fetch(r0, 2);
     asm volatile("" ::: "memory");
-    // metric of the tile's rows, for the epilogue
-    uint32_t *row_is_ip = (uint32_t *)(cg_lds + CG_LDS);
-    {
-        const uint32_t ml = tid < a_rows ? tid : a_rows - 1;
-        row_is_ip[tid] = row_metric ? row_metric[(size_t)(bm + ml) * metric_stride] : fixed_metric;
-    }
     __syncthreads();
 
     tri_f32x16 acc[4][2];
@@ -118,9 +122,12 @@ __device__ __forceinline__ void coarse_gemm_tile(
         fetch(ready, s + 3);
         __syncthreads();
     };
+    // (rows are multiples of 128 bytes: an even number of stages.  No "if there is a second one" here: a path through
+    // the loop that skips the second stage would have the compiler make the first stage's deposits wait for every load
+    // in flight, the set fetched one stage ago included)
     for (uint32_t s = 0; s < nsteps; s += 2) {
         stage(s, r1);
-        if (s + 1 < nsteps) stage(s + 1, r0);
+        stage(s + 1, r0);
     }
 
     // epilogue: accumulator r of lane l is (row 8*(r/4) + 4*(l/32) + r%4, col l%32) of its 32x32 block.
@@ -223,7 +230,7 @@ hipError_t tri_launch_coarse_gemm(hipStream_t s, int dtype, const void *a_rows, 
                                   float *scores, uint32_t ldc)
 {
     if (m == 0 || n == 0) return hipSuccess;
-    if (row_bytes == 0 || row_bytes % CG_KB != 0 || a_pitch_bytes % 16 != 0) return hipErrorInvalidValue;
+    if (row_bytes == 0 || row_bytes % (2 * CG_KB) != 0 || a_pitch_bytes % 16 != 0) return hipErrorInvalidValue;
     dim3 grid((n + CG_BN - 1) / CG_BN, (m + CG_BM - 1) / CG_BM);
     static bool lds_set[2] = {false, false};       // (more LDS than a kernel gets by default)
     const int v = dtype == TRI_DT_F16 ? 1 : 0;
