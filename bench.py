@@ -443,7 +443,9 @@ def pq_bench(args, tri, workloads, torch):
     """Side measurement: IVF search over product-quantised lists (include/trinity_pq.h) on configuration 2's data --
     1M x 768 fp16 unit-norm, inner product, nlist 4096 -- with m = 96 sub-spaces (96 bytes per vector instead of 1536),
     batches of 2048 queries, nprobe 32, k 10; by table scores alone and with the 100 / 256 best of them re-ranked by
-    exact scores.  Recall is against exact search over the stored vectors; `value` is the fastest mode that reaches
+    exact scores read from the tri_pq's own row-major copy of the vectors (pq_params.refine_rows: re-ranking gathers
+    whole rows by id, which the index's interleaved blocks, laid out for the list scan, serve badly).  Recall is
+    against exact search over the stored vectors; `value` is the fastest mode that reaches
     0.9 (the table-score mode if none does)."""
     from paper_2512_02281_amd import pq as tpq
     t_start = time.time()
@@ -457,7 +459,7 @@ def pq_bench(args, tri, workloads, torch):
                     flags=0, score_capacity=0, own_stream=True)
     index = pool.build_index(base_t, cfg.dim, cfg.nlist, tri.TRI_F16, tri.TRI_IP, 4, centroids=base_t[torch.from_numpy(rows.astype(np.int64)).cuda()].float().cpu().numpy())
     t0 = time.perf_counter()
-    pq = tpq.PQ(pool, index, m, train_iters=8, train_rows=65536, seed=1)
+    pq = tpq.PQ(pool, index, m, train_iters=8, train_rows=65536, seed=1, refine_rows=True)
     build_s = time.perf_counter() - t0
     ws = pq.workspace(nq)
     out = pq.search(queries_t, k, nprobe, tri.TRI_IP, ws=ws)
@@ -524,7 +526,7 @@ def pq_bench(args, tri, workloads, torch):
         "config": {"workload": f"side measurement: IVF over product-quantised lists on configs[2]'s data ({cfg.n_base} x {cfg.dim} f16, nlist {cfg.nlist}), "
                                f"m {m} sub-spaces of {cfg.dim // m}, {nq} queries per batch, nprobe {nprobe}, k {k}, inner product",
                    "queries_per_step": nq, "recall_at_k": recall, "recall_sample": rs, "bytes_per_vector": m,
-                   "short_list_for_exact_reranking": head["k_adc"], "modes": modes,
+                   "short_list_for_exact_reranking": head["k_adc"], "rows_for_reranking": "row-major copy by id (refine_rows)", "modes": modes,
                    "codes_scanned_per_batch": codes_scanned, "pq_build_s": round(build_s, 2), "query_vectors": "device-resident"},
         "roofline": {"bound": "lds", "achieved": round(achieved, 1), "peak": lds_peak, "unit": "GB/s", "frac": round(achieved / lds_peak, 4),
                      "traffic": None, "kernel": "pq_scan_kernel + the batch's four other launches (whole batch time)",

@@ -39,11 +39,15 @@ typedef struct {
                                the LDS beside the selection buffer (m <= 124)                                */
     uint32_t train_iters;   /* Lloyd iterations per sub-space when the codebooks are trained here            */
     uint32_t train_rows;    /* stored vectors the training uses (every n/train_rows-th one; 0 = min(n, 65536)) */
-    uint32_t pad_;
+    uint32_t refine_rows;   /* != 0: the tri_pq keeps its own copy of the index's vectors, row-major by vector id
+                               (n padded rows more of device memory), and re-ranking (k_adc > 0) reads those: one
+                               contiguous row per candidate instead of pieces scattered over a block of the index's
+                               interleaved lists (which are laid out for the list scan).  Same results.          */
     uint64_t seed;          /* picks the 256 vectors whose sub-vectors start the codebooks                   */
 } pq_params;
 
-/* Bytes pq_build needs: dev_bytes of device memory that the tri_pq keeps (codebooks, codes), tmp_bytes of device
+/* Bytes pq_build needs: dev_bytes of device memory that the tri_pq keeps (codebooks, codes, with
+ * refine_rows the vectors), tmp_bytes of device
  * memory it needs only during the call (training sums).  TRI_EINVAL for an m the index's dim does not allow. */
 int pq_build_bytes(const tri_index *index /*[host]*/, const pq_params *p /*[host]*/, size_t *dev_bytes /*[host] out*/,
                    size_t *tmp_bytes /*[host] out*/);

@@ -62,6 +62,16 @@ __device__ __forceinline__ float pq_elem(const TriIndexDev &ix, uint32_t slot, u
 }
 
 // ---------------------------------------------------------------------------------------- build
+// The index's vectors once more, row-major by vector id: one thread per 16-byte piece.
+__global__ void pq_refine_copy_kernel(const TriIndexDev ix, uint64_t n, uint8_t *__restrict__ refine)
+{
+    const uint32_t pieces = ix.row_bytes / 16;
+    const uint64_t t = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (t >= n * pieces) return;
+    const uint32_t id = (uint32_t)(t / pieces), j = (uint32_t)(t % pieces);
+    *(uint4 *)(refine + (size_t)id * ix.row_bytes + j * 16) = *(const uint4 *)(tri_slot_ptr(ix, ix.inv[id]) + (size_t)j * TRI_PIECE_PITCH);
+}
+
 // Stored position of training row r: every stride-th stored vector.
 __global__ void pq_init_kernel(const TriIndexDev ix, uint64_t n,
                                uint32_t m, uint32_t dsub, uint64_t seed, float *__restrict__ cb)
@@ -275,6 +285,7 @@ __global__ __launch_bounds__(PQ_THREADS) void pq_scan_kernel(const float *__rest
                                                              const uint8_t *__restrict__ codes, uint32_t k, uint32_t metric,
                                                              uint32_t k_adc, const uint8_t *__restrict__ qrows,
                                                              const uint8_t *__restrict__ vecs, const uint32_t *__restrict__ inv,
+                                                             const uint8_t *__restrict__ refine,
                                                              uint32_t row_bytes, uint32_t dtype,
                                                              uint32_t *__restrict__ ids_out, float *__restrict__ dist_out,
                                                              uint32_t *__restrict__ n_out)
@@ -348,18 +359,26 @@ __global__ __launch_bounds__(PQ_THREADS) void pq_scan_kernel(const float *__rest
     }
     pq_collect_settle(col, ksel);
     if (k_adc) {
-        // Re-ranking: the k_adc best by table scores are scored again exactly against the stored rows (found through
-        // the index's inverse id map) -- squared L2 in the difference form, or the inner product, fp32, one row per
+        // Re-ranking: the k_adc best by table scores are scored again exactly against the stored rows (the tri_pq's own
+        // row-major copy when it keeps one, else the index's blocks found through its slot map) -- squared L2 in the difference form, or the inner product, fp32, one row per
         // half-wavefront with a fixed reduction order -- and put in the order of those scores.
         const uint32_t have = col.have, l32 = threadIdx.x & 31;
         const uint8_t *qrow = qrows + (size_t)q * row_bytes;
         for (uint32_t i = threadIdx.x >> 5; i < have; i += PQ_THREADS / 32) {
             const uint32_t id = (uint32_t)(col.buf[i] & 0xFFFFFFFFu);
-            const uint32_t slot = inv[id];
-            const uint8_t *x = vecs + (size_t)(slot >> 5) * tri_block_stride(row_bytes) + (slot & 31u) * 16u;   // its pieces lie TRI_PIECE_PITCH apart
+            const uint8_t *x;
+            uint32_t piece_pitch;                                                  // distance between a row's 16-byte pieces
+            if (refine) {
+                x = refine + (size_t)id * row_bytes;
+                piece_pitch = 16u;
+            } else {
+                const uint32_t slot = inv[id];
+                x = vecs + (size_t)(slot >> 5) * tri_block_stride(row_bytes) + (slot & 31u) * 16u;
+                piece_pitch = TRI_PIECE_PITCH;
+            }
             float acc = 0.f;
             for (uint32_t o = l32 * 16; o < row_bytes; o += 32 * 16) {
-                const uint4 xv = *(const uint4 *)(x + (size_t)o * (TRI_PIECE_PITCH / 16)), qv = *(const uint4 *)(qrow + o);
+                const uint4 xv = *(const uint4 *)(x + (size_t)(o / 16) * piece_pitch), qv = *(const uint4 *)(qrow + o);
                 if (dtype == 1u) {
                     const _Float16 *xe = (const _Float16 *)&xv, *qe = (const _Float16 *)&qv;
 #pragma unroll
@@ -401,6 +420,7 @@ struct tri_pq {
     uint32_t dsub = 0;
     float *cb = nullptr;        // [m][dsub][256] (pq_cb_at)
     uint8_t *codes = nullptr;   // codes of the stored positions, in transposed blocks of 64 (pq_code_at)
+    uint8_t *refine = nullptr;  // pq_params.refine_rows: the vectors row-major by id (pitch row_bytes), else null
 };
 
 namespace {
@@ -430,7 +450,8 @@ extern "C" int pq_build_bytes(const tri_index *index, const pq_params *p, size_t
     uint32_t dsub = 0;
     const int rc = pq_check(v, p, &dsub);
     if (rc) return rc;
-    *dev_bytes = up256((size_t)p->m * TRI_PQ_KSUB * dsub * 4) + up256((size_t)(v.n + 63) / 64 * 64 * pq_mpad(p->m));
+    *dev_bytes = up256((size_t)p->m * TRI_PQ_KSUB * dsub * 4) + up256((size_t)(v.n + 63) / 64 * 64 * pq_mpad(p->m)) +
+                 (p->refine_rows ? up256((size_t)v.n * v.dev.row_bytes) : 0);
     *tmp_bytes = up256((size_t)p->m * TRI_PQ_KSUB * dsub * 4) + up256((size_t)p->m * TRI_PQ_KSUB * 4);
     return TRI_OK;
 }
@@ -456,6 +477,7 @@ extern "C" int pq_build(const tri_index *index, const pq_params *p, const float 
     const size_t cb_bytes = (size_t)m * TRI_PQ_KSUB * dsub * 4;
     Q->cb = (float *)dev_mem;
     Q->codes = (uint8_t *)dev_mem + up256(cb_bytes);
+    if (p->refine_rows) Q->refine = Q->codes + up256((size_t)(Q->view.n + 63) / 64 * 64 * pq_mpad(p->m));
     hipStream_t s = v.stream;
     auto fail = [&](int code) { delete Q; return code; };
 #define PQ_TRY_B(expr)                                                                                         \
@@ -497,6 +519,11 @@ extern "C" int pq_build(const tri_index *index, const pq_params *p, const float 
                        v.dev, v.n, (uint64_t)1, m, dsub, Q->cb, (float *)nullptr,
                        (uint32_t *)nullptr, Q->codes);
     PQ_TRY_B(hipGetLastError());
+    if (Q->refine) {
+        const uint64_t pieces = (uint64_t)v.n * (v.dev.row_bytes / 16);
+        hipLaunchKernelGGL(pq_refine_copy_kernel, dim3((unsigned)((pieces + 255) / 256)), dim3(256), 0, s, v.dev, v.n, Q->refine);
+        PQ_TRY_B(hipGetLastError());
+    }
     PQ_TRY_B(hipStreamSynchronize(s));
 #undef PQ_TRY_B
     *out = Q;
@@ -606,7 +633,7 @@ extern "C" int pq_search_batch(tri_pq *pq, const void *queries, size_t pitch_byt
     hipLaunchKernelGGL(pq_lut_kernel, dim3(nq), dim3(PQ_THREADS), 0, s, w.qrows, d.row_bytes, d.dtype, m, pq->dsub, metric, pq->cb, w.lut);
     PQ_TRY(hipGetLastError());
     hipLaunchKernelGGL(pq_scan_kernel, dim3(nq), dim3(PQ_THREADS), lut_bytes, s, w.lut, m, probes, nprobe, d.list_off, d.ids, pq->codes,
-                       k, metric, k_adc, w.qrows, (const uint8_t *)d.vecs, d.inv, d.row_bytes, d.dtype, ids_out, dist_out, n_out);
+                       k, metric, k_adc, w.qrows, (const uint8_t *)d.vecs, d.inv, (const uint8_t *)pq->refine, d.row_bytes, d.dtype, ids_out, dist_out, n_out);
     PQ_TRY(hipGetLastError());
     return TRI_OK;
 }

@@ -18,7 +18,7 @@ TRI_PQ_DSUB_MAX = 32
 
 class pq_params(ctypes.Structure):
     _fields_ = [("m", ctypes.c_uint32), ("train_iters", ctypes.c_uint32), ("train_rows", ctypes.c_uint32),
-                ("pad_", ctypes.c_uint32), ("seed", ctypes.c_uint64)]
+                ("refine_rows", ctypes.c_uint32), ("seed", ctypes.c_uint64)]
 
 
 def _bind():
@@ -46,10 +46,10 @@ class PQ:
     """Codebooks and codes of an index of a living Pool (the Pool owns the stream; this object the device memory)."""
 
     def __init__(self, pool, index: int, m: int, train_iters: int = 8, train_rows: int = 0, seed: int = 0,
-                 codebooks: Optional[np.ndarray] = None):
+                 codebooks: Optional[np.ndarray] = None, refine_rows: bool = False):
         import torch
         self.pool, self.index = pool, index
-        self.params = pq_params(m, train_iters, train_rows, 0, seed)
+        self.params = pq_params(m, train_iters, train_rows, 1 if refine_rows else 0, seed)
         dev, tmp = ctypes.c_size_t(0), ctypes.c_size_t(0)
         _check(_lib.pq_build_bytes(ctypes.c_void_p(index), ctypes.byref(self.params), ctypes.byref(dev), ctypes.byref(tmp)), "pq_build_bytes")
         self._mem = pool._device_bytes(dev.value)

@@ -185,19 +185,21 @@ def test_edge_cases_and_argument_errors():
             assert ei.value.status == tri.TRI_ENOMEM
 
 
-@pytest.mark.parametrize("dtype,d,m", [("f16", 768, 96), ("f32", 128, 16)])
-def test_reranked_search_against_the_two_stage_oracle(dtype, d, m):
+@pytest.mark.parametrize("dtype,d,m,refine", [("f16", 768, 96, False), ("f32", 128, 16, False), ("f16", 768, 96, True), ("f32", 128, 16, True)])
+def test_reranked_search_against_the_two_stage_oracle(dtype, d, m, refine):
     """k_adc > 0: the short list chosen by table sums is re-ranked by exact scores against the stored rows.  Where
     the short list ends, table sums within rounding of each other may be cut either way, so the check is the
     tie-aware one of both stages: every returned id belongs to a short list the oracle allows (its table score is not
     worse than the oracle's k_adc-th beyond the tolerance), carries its exact score, the order is by exact score, and
-    no candidate that is surely in the short list and surely better than the returned k-th is missing."""
+    no candidate that is surely in the short list and surely better than the returned k-th is missing.
+    refine: the tri_pq re-ranks from its own row-major copy of the vectors (pq_params.refine_rows); beside the oracle
+    check, its answers must be bit for bit those of a tri_pq with the same codebooks that reads the index's blocks."""
     tri = harness.lib()
     from paper_2512_02281_amd import pq as tpq
     n, nlist = 16_000, 24
     rng, base, pool, idx, oidx, torch = _setup(tri, dtype, n, d, nlist, seed=700 + d)
     tol = checker.tolerance_for(oidx.dtype)
-    with pool, tpq.PQ(pool, idx, m, train_iters=4, train_rows=4000, seed=5) as pq:
+    with pool, tpq.PQ(pool, idx, m, train_iters=4, train_rows=4000, seed=5, refine_rows=refine) as pq:
         cb, codes = pq.export(n, d)
         nq = 32
         queries = np.ascontiguousarray((base[rng.choice(n, nq)].astype(np.float64) + rng.normal(0, 0.3, size=(nq, d))).astype(base.dtype))
@@ -205,6 +207,12 @@ def test_reranked_search_against_the_two_stage_oracle(dtype, d, m):
         for k, k_adc, nprobe, metric in [(10, 100, 6, 0), (10, 256, 8, 1), (5, 5, 3, 1), (64, 200, nlist, 0)]:
             ids, dist, n_out, probes = _to_host(*pq.search(qt, k, nprobe, metric, k_adc=k_adc))
             pq.sync()
+            if refine:
+                with tpq.PQ(pool, idx, m, codebooks=cb) as plain:
+                    ids2, dist2, n_out2, probes2 = _to_host(*plain.search(qt, k, nprobe, metric, k_adc=k_adc))
+                    plain.sync()
+                assert np.array_equal(ids, ids2) and np.array_equal(n_out, n_out2) and np.array_equal(probes, probes2)
+                assert np.array_equal(dist.view(np.uint32), dist2.view(np.uint32))
             changed = 0
             for i in range(nq):
                 q = queries[i]
