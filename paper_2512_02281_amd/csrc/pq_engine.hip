@@ -165,18 +165,44 @@ struct PqCollector {
     uint32_t count;        // composites in buf
     uint32_t have;         // of which sorted best (the first `have`)
     uint64_t bound;        // the k-th best when have == k, else all-ones
+    uint64_t wave_kth[PQ_THREADS / 64];   // first round: per wavefront, the last of its smallest offers that are kept
 };
 
-// Bitonic sort of buf[0..n) ascending (n <= PQ_BUF, padded with all-ones to a power of two); all threads.
+// One compare-exchange step of a bitonic network among the 64 lanes of a wavefront: lanes l and l ^ s.
+__device__ __forceinline__ uint64_t pq_cx(uint64_t x, uint32_t lane, uint32_t s, bool up)
+{
+    const uint32_t lo = (uint32_t)__shfl_xor((int)(uint32_t)x, (int)s, 64), hi = (uint32_t)__shfl_xor((int)(uint32_t)(x >> 32), (int)s, 64);
+    const uint64_t o = ((uint64_t)hi << 32) | lo;
+    const bool take_min = ((lane & s) == 0) == up;            // the lower lane of an ascending pair keeps the smaller one
+    return take_min ? (o < x ? o : x) : (o > x ? o : x);
+}
+
+// Bitonic sort of a[0..n) ascending (n <= PQ_BUF, padded with all-ones to a power of two >= 64); all NT threads.
+// The steps whose partners lie less than 64 apart -- most of them -- are done in registers, a wavefront per chunk of
+// 64 with lane exchanges and no barrier; only the steps with farther partners go through LDS, one barrier each.
+template <uint32_t NT = PQ_THREADS>
 __device__ void pq_sort(uint64_t *a, uint32_t n)
 {
-    uint32_t np2 = 1;
+    constexpr uint32_t NW = NT / 64;
+    uint32_t np2 = 64;
     while (np2 < n) np2 <<= 1;
-    for (uint32_t i = n + threadIdx.x; i < np2; i += PQ_THREADS) a[i] = ~0ull;
+    for (uint32_t i = n + threadIdx.x; i < np2; i += NT) a[i] = ~0ull;
     __syncthreads();
-    for (uint32_t size = 2; size <= np2; size <<= 1)
-        for (uint32_t stride = size >> 1; stride > 0; stride >>= 1) {
-            for (uint32_t i = threadIdx.x; i < np2 / 2; i += PQ_THREADS) {
+    const uint32_t lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    for (uint32_t i = wave * 64 + lane; i < np2; i += NW * 64) {             // sizes 2 .. 64
+        uint64_t x = a[i];
+#pragma unroll
+        for (uint32_t size = 2; size <= 64; size <<= 1) {
+            const bool up = (i & size) == 0;
+#pragma unroll
+            for (uint32_t s = size >> 1; s > 0; s >>= 1) x = pq_cx(x, lane, s, up);
+        }
+        a[i] = x;
+    }
+    __syncthreads();
+    for (uint32_t size = 128; size <= np2; size <<= 1) {
+        for (uint32_t stride = size >> 1; stride >= 64; stride >>= 1) {
+            for (uint32_t i = threadIdx.x; i < np2 / 2; i += NT) {
                 const uint32_t lo = 2 * i - (i & (stride - 1)), hi = lo + stride;
                 const bool up = (lo & size) == 0;
                 const uint64_t x = a[lo], y = a[hi];
@@ -187,6 +213,15 @@ __device__ void pq_sort(uint64_t *a, uint32_t n)
             }
             __syncthreads();
         }
+        for (uint32_t i = wave * 64 + lane; i < np2; i += NW * 64) {
+            uint64_t x = a[i];
+            const bool up = (i & size) == 0;
+#pragma unroll
+            for (uint32_t s = 32; s > 0; s >>= 1) x = pq_cx(x, lane, s, up);
+            a[i] = x;
+        }
+        __syncthreads();
+    }
 }
 
 __device__ __forceinline__ void pq_collect_init(PqCollector &c)
@@ -200,11 +235,12 @@ __device__ __forceinline__ void pq_collect_init(PqCollector &c)
 }
 
 // Sort what was collected and keep the k best.  All threads; ends with a barrier.
+template <uint32_t NT = PQ_THREADS>
 __device__ void pq_collect_settle(PqCollector &c, uint32_t k)
 {
     __syncthreads();
     const uint32_t n = c.count;
-    pq_sort(c.buf, n);
+    pq_sort<NT>(c.buf, n);
     if (threadIdx.x == 0) {
         c.have = n < k ? n : k;
         c.count = c.have;
@@ -213,10 +249,11 @@ __device__ void pq_collect_settle(PqCollector &c, uint32_t k)
     __syncthreads();
 }
 
-// One round of offers: every thread may offer one composite (valid = it has one).  All threads call it together.
-// Whether the array could take another round is decided by all threads as one: the barrier that ends the round also
-// combines what each thread saw of the counter after its own append (the thread that appended last saw them all).
-__device__ __forceinline__ void pq_collect_round(PqCollector &c, uint32_t k, bool valid, uint64_t comp)
+// A round of offers: every thread offers composites (pq_collect_offer: valid = it has one; no barrier), then all
+// threads call pq_collect_close together, `room` = the offers the next round may bring at most.  Whether the array
+// could take that round is decided by all threads as one: the barrier that ends the round also combines what each
+// thread saw of the counter after its own appends (the thread that appended last saw them all).
+__device__ __forceinline__ void pq_collect_offer(PqCollector &c, bool valid, uint64_t comp)
 {
     // one counter update per wavefront, not per lane: before the first bound exists every lane appends
     const bool push = valid && comp < c.bound;
@@ -229,56 +266,146 @@ __device__ __forceinline__ void pq_collect_round(PqCollector &c, uint32_t k, boo
         base = (uint32_t)__shfl((int)base, leader, 64);
         if (push) c.buf[base + (uint32_t)__popcll(mask & ((1ull << lane) - 1ull))] = comp;
     }
+}
+template <uint32_t NT = PQ_THREADS>
+__device__ __forceinline__ void pq_collect_close(PqCollector &c, uint32_t k, uint32_t room)
+{
     // settle when the array could not take another round -- or as soon as k composites are there and no bound yet:
     // from then on only offers that beat the k-th best are appended
-    if (__syncthreads_or(c.count + PQ_THREADS > PQ_BUF || (c.have < k && c.count >= k))) pq_collect_settle(c, k);
+    if (__syncthreads_or(c.count + room > PQ_BUF || (c.have < k && c.count >= k))) pq_collect_settle<NT>(c, k);
+}
+template <uint32_t NT = PQ_THREADS>
+__device__ __forceinline__ void pq_collect_round(PqCollector &c, uint32_t k, bool valid, uint64_t comp)
+{
+    pq_collect_offer(c, valid, comp);
+    pq_collect_close<NT>(c, k, NT);
 }
 
-// (3) the nprobe best lists of each query: best first, ties to the smaller list number.
-__global__ __launch_bounds__(PQ_THREADS) void pq_probe_kernel(const float *__restrict__ scores, uint32_t ldc, uint32_t nlist,
+// The first round of a selection, when no bound exists yet and every offer would be appended (and the first settle
+// would sort them all): whether this thread's offer has to be kept.  Every wavefront finds the j-th smallest of its 64
+// offers, j = ceil(k / wavefronts), by rank counting across its lanes; the largest of these over the wavefronts has at
+// least k offers of this round at or below it, so an offer above it is dropped exactly.  A wavefront with fewer than
+// j offers makes every offer kept.  All threads call it together (one barrier).
+template <uint32_t NT = PQ_THREADS>
+__device__ __forceinline__ bool pq_first_round_keeps(PqCollector &c, uint32_t k, bool valid, uint64_t comp)
+{
+    constexpr uint32_t NW = NT / 64;
+    const uint32_t lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const uint32_t j = (k + NW - 1) / NW;                          // (1 <= j <= 64: k <= 64 NW)
+    const uint64_t mine = valid ? comp : ~0ull;
+    const uint32_t lo = (uint32_t)mine, hi = (uint32_t)(mine >> 32);
+    uint32_t rank = 0;
+#pragma unroll
+    for (int i = 0; i < 64; ++i) {
+        const uint64_t o = ((uint64_t)(uint32_t)__builtin_amdgcn_readlane((int)hi, i) << 32) | (uint32_t)__builtin_amdgcn_readlane((int)lo, i);
+        rank += o < mine ? 1u : 0u;
+    }
+    const uint64_t hit = __ballot(valid && rank == j - 1);
+    uint64_t kth = ~0ull;
+    if (hit) {
+        const int src = __ffsll((unsigned long long)hit) - 1;
+        kth = ((uint64_t)(uint32_t)__shfl((int)hi, src, 64) << 32) | (uint32_t)__shfl((int)lo, src, 64);
+    }
+    if (lane == 0) c.wave_kth[wave] = kth;
+    __syncthreads();
+    uint64_t pre = 0;
+#pragma unroll
+    for (uint32_t w = 0; w < NW; ++w) pre = c.wave_kth[w] > pre ? c.wave_kth[w] : pre;
+    return valid && mine <= pre;
+}
+
+// (3) the nprobe best lists of each query: best first, ties to the smaller list number.  (Small workgroups: the first
+// settle, which gives the bound that turns most later offers away, then sorts 256 composites instead of 1024, and
+// several workgroups share a compute unit.)
+constexpr uint32_t PQ_PROBE_THREADS = 256, PQ_PROBE_R = 4;
+__global__ __launch_bounds__(PQ_PROBE_THREADS) void pq_probe_kernel(const float *__restrict__ scores, uint32_t ldc, uint32_t nlist,
                                                               uint32_t nprobe, uint32_t metric, uint32_t *__restrict__ probes)
 {
     __shared__ PqCollector col;
     const float *row = scores + (size_t)blockIdx.x * ldc;
+    const uint32_t kind = metric == 1u ? 1u : 0u;
     pq_collect_init(col);
-    for (uint32_t i0 = 0; i0 < nlist; i0 += PQ_THREADS) {
-        const uint32_t i = i0 + threadIdx.x;
-        const bool valid = i < nlist;
-        const uint64_t comp = valid ? ((uint64_t)tri_score_key(row[i], metric == 1u ? 1u : 0u) << 32) | i : ~0ull;
-        pq_collect_round(col, nprobe, valid, comp);
+    {   // the first 256 scores: they give the bound
+        const bool valid = threadIdx.x < nlist;
+        const uint64_t comp = valid ? ((uint64_t)tri_score_key(row[threadIdx.x], kind) << 32) | threadIdx.x : ~0ull;
+        pq_collect_offer(col, pq_first_round_keeps<PQ_PROBE_THREADS>(col, nprobe, valid, comp), comp);
+        pq_collect_close<PQ_PROBE_THREADS>(col, nprobe, PQ_PROBE_R * PQ_PROBE_THREADS);
     }
-    pq_collect_settle(col, nprobe);
-    for (uint32_t i = threadIdx.x; i < nprobe; i += PQ_THREADS)
+    // then PQ_PROBE_R scores per thread and round (their loads in flight together, one barrier for all of them)
+    for (uint32_t i0 = PQ_PROBE_THREADS; i0 < nlist; i0 += PQ_PROBE_R * PQ_PROBE_THREADS) {
+        float v[PQ_PROBE_R];
+#pragma unroll
+        for (uint32_t r = 0; r < PQ_PROBE_R; ++r) {
+            const uint32_t i = i0 + r * PQ_PROBE_THREADS + threadIdx.x;
+            v[r] = i < nlist ? row[i] : 0.f;
+        }
+#pragma unroll
+        for (uint32_t r = 0; r < PQ_PROBE_R; ++r) {
+            const uint32_t i = i0 + r * PQ_PROBE_THREADS + threadIdx.x;
+            pq_collect_offer(col, i < nlist, ((uint64_t)tri_score_key(v[r], kind) << 32) | i);
+        }
+        pq_collect_close<PQ_PROBE_THREADS>(col, nprobe, PQ_PROBE_R * PQ_PROBE_THREADS);
+    }
+    pq_collect_settle<PQ_PROBE_THREADS>(col, nprobe);
+    for (uint32_t i = threadIdx.x; i < nprobe; i += PQ_PROBE_THREADS)
         probes[(size_t)blockIdx.x * nprobe + i] = i < col.have ? (uint32_t)(col.buf[i] & 0xFFFFFFFFu) : 0xFFFFFFFFu;
 }
 
-// (4) tables: lut[q][mm][c] = sum over the sub-space of (q - entry)^2, or of -q * entry, in coordinate order.
-__global__ __launch_bounds__(PQ_THREADS) void pq_lut_kernel(const uint8_t *__restrict__ qrows, uint32_t row_bytes, uint32_t dtype,
-                                                            uint32_t m, uint32_t dsub, uint32_t metric,
-                                                            const float *__restrict__ cb, float *__restrict__ lut)
+// (4) tables: lut[q][mm][c] = sum over the sub-space of (q - entry)^2, or of -q * entry, in coordinate order.  A
+// workgroup makes the tables of PQ_LUT_Q queries for PQ_LUT_M sub-spaces (grid: query groups x m / PQ_LUT_M; m is a
+// multiple of 4): a codebook word read from the cache serves all its queries, a thread's codebook loads of its
+// PQ_LUT_M entries are all in flight together, and the kernel is left with writing the tables.
+constexpr uint32_t PQ_LUT_Q = 16, PQ_LUT_M = 4;
+__global__ __launch_bounds__(TRI_PQ_KSUB) void pq_lut_kernel(const uint8_t *__restrict__ qrows, uint32_t row_bytes, uint32_t dtype,
+                                                             uint32_t nq, uint32_t m, uint32_t dsub, uint32_t metric,
+                                                             const float *__restrict__ cb, float *__restrict__ lut)
 {
-    __shared__ float qv[TRI_PQ_DSUB_MAX * 128];              // the query's dim <= 32 * 124 values
-    const uint32_t q = blockIdx.x;
-    const uint8_t *row = qrows + (size_t)q * row_bytes;
-    for (uint32_t i = threadIdx.x; i < m * dsub; i += PQ_THREADS) qv[i] = dtype == 1u ? (float)((const _Float16 *)row)[i] : ((const float *)row)[i];
+    __shared__ __attribute__((aligned(16))) float qv[PQ_LUT_Q][PQ_LUT_M * TRI_PQ_DSUB_MAX];
+    const uint32_t q0 = blockIdx.x * PQ_LUT_Q, m0 = blockIdx.y * PQ_LUT_M, c = threadIdx.x, span = PQ_LUT_M * dsub;
+    for (uint32_t i = threadIdx.x; i < PQ_LUT_Q * span; i += TRI_PQ_KSUB) {
+        const uint32_t j = i / span, e = i % span;
+        const uint8_t *row = qrows + (size_t)(q0 + j < nq ? q0 + j : q0) * row_bytes;
+        qv[j][e] = dtype == 1u ? (float)((const _Float16 *)row)[m0 * dsub + e] : ((const float *)row)[m0 * dsub + e];
+    }
     __syncthreads();
-    for (uint32_t t = threadIdx.x; t < m * TRI_PQ_KSUB; t += PQ_THREADS) {
-        const uint32_t mm = t / TRI_PQ_KSUB, c = t % TRI_PQ_KSUB;
-        float acc = 0.f;
-        for (uint32_t e = 0; e < dsub; ++e) {
-            const float x = qv[mm * dsub + e], y = cb[pq_cb_at(mm, c, e, dsub)];
-            if (metric == 0u) {
-                const float d = x - y;
-                acc = __builtin_fmaf(d, d, acc);
-            } else {
-                acc = __builtin_fmaf(-x, y, acc);
+    auto term = [&](float x, float y, float a) {
+        const float d = x - y;
+        return metric == 0u ? __builtin_fmaf(d, d, a) : __builtin_fmaf(-x, y, a);
+    };
+#pragma unroll
+    for (uint32_t u = 0; u < PQ_LUT_M; ++u) {
+        const uint32_t mm = m0 + u;
+        float acc[PQ_LUT_Q];
+#pragma unroll
+        for (uint32_t j = 0; j < PQ_LUT_Q; ++j) acc[j] = 0.f;
+        if (dsub % 4 == 0) {
+            // (the query values are the same for all lanes and come four to a read)
+            for (uint32_t e = 0; e < dsub; e += 4) {
+                float y[4];
+#pragma unroll
+                for (uint32_t i = 0; i < 4; ++i) y[i] = cb[pq_cb_at(mm, c, e + i, dsub)];
+#pragma unroll
+                for (uint32_t j = 0; j < PQ_LUT_Q; ++j) {
+                    const float4 x = *(const float4 *)&qv[j][u * dsub + e];
+                    acc[j] = term(x.w, y[3], term(x.z, y[2], term(x.y, y[1], term(x.x, y[0], acc[j]))));
+                }
+            }
+        } else {
+            for (uint32_t e = 0; e < dsub; ++e) {
+                const float y = cb[pq_cb_at(mm, c, e, dsub)];
+#pragma unroll
+                for (uint32_t j = 0; j < PQ_LUT_Q; ++j) acc[j] = term(qv[j][u * dsub + e], y, acc[j]);
             }
         }
-        lut[(size_t)q * m * TRI_PQ_KSUB + t] = acc;
+#pragma unroll
+        for (uint32_t j = 0; j < PQ_LUT_Q; ++j)
+            if (q0 + j < nq) lut[((size_t)(q0 + j) * m + mm) * TRI_PQ_KSUB + c] = acc[j];
     }
 }
 
-// (5) one workgroup per query.
+// (5) one workgroup per query.  G: the 16-byte groups of a code when m is a multiple of 16 (the look-ups of a code are
+// then one straight run of instructions), 0 for any other m.
+template <uint32_t G>
 __global__ __launch_bounds__(PQ_THREADS) void pq_scan_kernel(const float *__restrict__ lut, uint32_t m,
                                                              const uint32_t *__restrict__ probes, uint32_t nprobe,
                                                              const uint32_t *__restrict__ list_off, const uint32_t *__restrict__ ids,
@@ -299,62 +426,97 @@ __global__ __launch_bounds__(PQ_THREADS) void pq_scan_kernel(const float *__rest
 #pragma unroll 4
         for (uint32_t t = threadIdx.x; t < m * (TRI_PQ_KSUB / 4); t += PQ_THREADS) ((float4 *)lut_lds)[t] = src[t];
     }
-    if (threadIdx.x == 0) {
-        uint32_t run = 0;
-        for (uint32_t p = 0; p < nprobe; ++p) {
-            const uint32_t l = probes[(size_t)q * nprobe + p];
-            first[p] = l == 0xFFFFFFFFu ? 0u : list_off[l];
-            start[p] = run;
-            run += l == 0xFFFFFFFFu ? 0u : list_off[l + 1] - list_off[l];
+    if (threadIdx.x < 64) {
+        // (the first wavefront: lane l takes probes 4 l .. 4 l + 3, the running sums come from a scan across the lanes)
+        constexpr uint32_t PER = TRI_PQ_NPROBE_MAX / 64;
+        uint32_t len[PER], mine = 0;
+#pragma unroll
+        for (uint32_t j = 0; j < PER; ++j) {
+            const uint32_t p = threadIdx.x * PER + j;
+            const uint32_t l = p < nprobe ? probes[(size_t)q * nprobe + p] : 0xFFFFFFFFu;
+            const uint32_t lo = l == 0xFFFFFFFFu ? 0u : list_off[l], hi = l == 0xFFFFFFFFu ? 0u : list_off[l + 1];
+            if (p < nprobe) first[p] = lo;
+            len[j] = hi - lo;
+            mine += len[j];
         }
-        start[nprobe] = run;
+        uint32_t incl = mine;
+#pragma unroll
+        for (int dd = 1; dd < 64; dd <<= 1) {
+            const uint32_t o = (uint32_t)__shfl_up((int)incl, dd, 64);
+            if ((int)threadIdx.x >= dd) incl += o;
+        }
+        uint32_t run = incl - mine;
+#pragma unroll
+        for (uint32_t j = 0; j < PER; ++j) {
+            const uint32_t p = threadIdx.x * PER + j;
+            if (p < nprobe) start[p] = run;
+            run += len[j];
+        }
+        if (threadIdx.x == 63) start[nprobe] = run;             // (the total: probes past nprobe count nothing)
     }
     pq_collect_init(col);
     // the vectors of all probed lists as ONE sequence (short lists would otherwise leave most of a round's threads
     // idle): thread t of a round takes element r0 + t and finds its list by bisection in the running sums
-    const uint32_t groups = pq_mpad(m) / 16, total = start[nprobe];
+    const uint32_t groups = G ? G : pq_mpad(m) / 16, total = start[nprobe];
     const uint32_t ksel = k_adc ? k_adc : k;              // how many the table scores select
-    for (uint32_t r0 = 0; r0 < total; r0 += PQ_THREADS) {
-        const uint32_t e = r0 + threadIdx.x;
-        const bool valid = e < total;
-        uint32_t v = 0;
-        if (valid) {
-            uint32_t lo = 0, hi = nprobe;                                  // start[lo] <= e < start[hi]
-            while (hi - lo > 1) {
-                const uint32_t mid = (lo + hi) / 2;
-                if (start[mid] <= e) lo = mid; else hi = mid;
-            }
-            v = first[lo] + (e - start[lo]);
+    // The codes (and the id) of a round's element are fetched one round ahead: the loads of round r + 1 are in flight
+    // while round r does its look-ups and its offer, which ends in a barrier.
+    auto locate = [&](uint32_t e) -> uint32_t {
+        uint32_t lo = 0, hi = nprobe;                                      // start[lo] <= e < start[hi]
+        while (hi - lo > 1) {
+            const uint32_t mid = (lo + hi) / 2;
+            if (start[mid] <= e) lo = mid; else hi = mid;
         }
-        float sum = 0.f;
-        if (valid) {
+        return first[lo] + (e - start[lo]);
+    };
+    uint4 cw_next[PQ_GROUPS_MAX];
+    uint32_t id_next = 0;
+    auto fetch = [&](uint32_t e) {
+        if (e < total) {
+            const uint32_t v = locate(e);
             const uint4 *code = (const uint4 *)(codes + pq_code_at(v, 0, m));
-            uint4 cw[PQ_GROUPS_MAX];
 #pragma unroll
             for (uint32_t g = 0; g < PQ_GROUPS_MAX; ++g)
-                if (g < groups) cw[g] = code[g * 64];                          // (uniform; all loads before the first look-up)
+                if (g < groups) cw_next[g] = code[g * 64];                     // (uniform)
+            id_next = ids[v];
+        }
+    };
+    fetch(threadIdx.x);
+    for (uint32_t r0 = 0; r0 < total; r0 += PQ_THREADS) {
+        const bool valid = r0 + threadIdx.x < total;
+        uint4 cw[PQ_GROUPS_MAX];
+#pragma unroll
+        for (uint32_t g = 0; g < PQ_GROUPS_MAX; ++g) cw[g] = cw_next[g];
+        const uint32_t id = id_next;
+        fetch(r0 + PQ_THREADS + threadIdx.x);
+        float sum = 0.f;
+        if (valid) {
+            // four look-ups for the four code bytes of a word (sub-spaces mm .. mm + 3), added in sub-space order
+            auto look4 = [&](uint32_t word, uint32_t mm) {
+                const float *t = lut_lds + (size_t)mm * TRI_PQ_KSUB;
+                const float a = t[word & 0xFFu], b = t[TRI_PQ_KSUB + ((word >> 8) & 0xFFu)];
+                const float c = t[2 * TRI_PQ_KSUB + ((word >> 16) & 0xFFu)], d = t[3 * TRI_PQ_KSUB + (word >> 24)];
+                sum = (((sum + a) + b) + c) + d;
+            };
 #pragma unroll
             for (uint32_t g = 0; g < PQ_GROUPS_MAX; ++g) {
-                if (g < groups) {
-                    const uint32_t w4[4] = {cw[g].x, cw[g].y, cw[g].z, cw[g].w};
-#pragma unroll
-                    for (uint32_t w = 0; w < 4; ++w) {
-                        const uint32_t mm = g * 16 + w * 4;
-                        if (mm < m) {                                              // (uniform: m is a multiple of 4)
-                            const float *t = lut_lds + (size_t)mm * TRI_PQ_KSUB;
-                            sum += t[w4[w] & 0xFFu];
-                            sum += t[TRI_PQ_KSUB + ((w4[w] >> 8) & 0xFFu)];
-                            sum += t[2 * TRI_PQ_KSUB + ((w4[w] >> 16) & 0xFFu)];
-                            sum += t[3 * TRI_PQ_KSUB + (w4[w] >> 24)];
-                        }
+                if (g < groups) {                                                  // (uniform, as is all of m)
+                    if (G || g * 16 + 16 <= m) {                                        // a whole group: 16 look-ups with nothing between them
+                        look4(cw[g].x, g * 16);
+                        look4(cw[g].y, g * 16 + 4);
+                        look4(cw[g].z, g * 16 + 8);
+                        look4(cw[g].w, g * 16 + 12);
+                    } else {                                                       // the last one of an m that is no multiple of 16
+                        look4(cw[g].x, g * 16);
+                        if (g * 16 + 4 < m) look4(cw[g].y, g * 16 + 4);
+                        if (g * 16 + 8 < m) look4(cw[g].z, g * 16 + 8);
                     }
                 }
             }
         }
         const uint32_t key = tri_score_key(sum, 0u);
-        // (the id is fetched only for a vector whose key alone does not rule it out)
-        const bool maybe = valid && ((uint64_t)key << 32) <= col.bound;
-        const uint64_t comp = maybe ? ((uint64_t)key << 32) | ids[v] : ~0ull;
+        const uint64_t comp = ((uint64_t)key << 32) | id;
+        const bool maybe = r0 == 0 ? pq_first_round_keeps(col, ksel, valid, comp) : valid && ((uint64_t)key << 32) <= col.bound;
         pq_collect_round(col, ksel, maybe, comp);
     }
     pq_collect_settle(col, ksel);
@@ -432,7 +594,7 @@ int pq_check(const TriIndexView &v, const pq_params *p, uint32_t *dsub)
     if (p->m == 0 || p->m % 4 != 0 || dim % p->m != 0)
         return tri_fail(TRI_EINVAL, "m = %u must be a multiple of 4 that divides dim = %u", p->m, dim);
     if (dim / p->m > TRI_PQ_DSUB_MAX) return tri_fail(TRI_EINVAL, "dim / m = %u exceeds %u", dim / p->m, TRI_PQ_DSUB_MAX);
-    if ((size_t)p->m * TRI_PQ_KSUB * 4 + sizeof(PqCollector) + 1024 > 160u * 1024u)
+    if ((size_t)p->m * TRI_PQ_KSUB * 4 + sizeof(PqCollector) + (2 * TRI_PQ_NPROBE_MAX + 1) * 4 + 64 > 160u * 1024u)   // (+ the list table)
         return tri_fail(TRI_EINVAL, "m = %u: the tables of a query (%u KiB) do not fit the LDS beside the selection buffer",
                         p->m, p->m * TRI_PQ_KSUB * 4 / 1024);
     if (v.n < TRI_PQ_KSUB) return tri_fail(TRI_EINVAL, "the index holds %llu vectors, fewer than a codebook has entries", (unsigned long long)v.n);
@@ -617,10 +779,16 @@ extern "C" int pq_search_batch(tri_pq *pq, const void *queries, size_t pitch_byt
     hipStream_t s = pq->view.stream;
     const uint32_t m = pq->p.m, ldc = tri_coarse_ldc(d.nlist);
     const uint32_t lut_bytes = m * TRI_PQ_KSUB * 4;
-    static uint32_t lds_limit = 0;          // (more LDS than a kernel gets by default: raised once per growth)
-    if (lut_bytes > lds_limit) {
-        PQ_TRY(hipFuncSetAttribute((const void *)pq_scan_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lut_bytes));
-        lds_limit = lut_bytes;
+    typedef void (*scan_fn)(const float *, uint32_t, const uint32_t *, uint32_t, const uint32_t *, const uint32_t *, const uint8_t *,
+                            uint32_t, uint32_t, uint32_t, const uint8_t *, const uint8_t *, const uint32_t *, const uint8_t *, uint32_t,
+                            uint32_t, uint32_t *, float *, uint32_t *);
+    static const scan_fn scans[PQ_GROUPS_MAX + 1] = {pq_scan_kernel<0>, pq_scan_kernel<1>, pq_scan_kernel<2>, pq_scan_kernel<3>, pq_scan_kernel<4>,
+                                                     pq_scan_kernel<5>, pq_scan_kernel<6>, pq_scan_kernel<7>, pq_scan_kernel<8>};
+    const uint32_t variant = m % 16 == 0 ? m / 16 : 0;
+    static uint32_t lds_limit[PQ_GROUPS_MAX + 1] = {};          // (more LDS than a kernel gets by default: raised once per growth)
+    if (lut_bytes > lds_limit[variant]) {
+        PQ_TRY(hipFuncSetAttribute((const void *)scans[variant], hipFuncAttributeMaxDynamicSharedMemorySize, (int)lut_bytes));
+        lds_limit[variant] = lut_bytes;
     }
     hipLaunchKernelGGL(pq_pad_queries_kernel, dim3(nq), dim3(256), 0, s, (const uint8_t *)queries, pitch_bytes, nq, d.dim * es,
                        d.row_bytes, w.qrows);
@@ -628,11 +796,12 @@ extern "C" int pq_search_batch(tri_pq *pq, const void *queries, size_t pitch_byt
     PQ_TRY(tri_launch_coarse_gemm(s, d.dtype == 1u ? 1 : 0, w.qrows, d.row_bytes, nq, d.centroids, d.cnorm, d.nlist, d.row_bytes,
                                   nullptr, 0u, metric, w.scores, ldc));
     uint32_t *probes = probes_out ? probes_out : w.probes;
-    hipLaunchKernelGGL(pq_probe_kernel, dim3(nq), dim3(PQ_THREADS), 0, s, w.scores, ldc, d.nlist, nprobe, metric, probes);
+    hipLaunchKernelGGL(pq_probe_kernel, dim3(nq), dim3(PQ_PROBE_THREADS), 0, s, w.scores, ldc, d.nlist, nprobe, metric, probes);
     PQ_TRY(hipGetLastError());
-    hipLaunchKernelGGL(pq_lut_kernel, dim3(nq), dim3(PQ_THREADS), 0, s, w.qrows, d.row_bytes, d.dtype, m, pq->dsub, metric, pq->cb, w.lut);
+    hipLaunchKernelGGL(pq_lut_kernel, dim3((nq + PQ_LUT_Q - 1) / PQ_LUT_Q, m / PQ_LUT_M), dim3(TRI_PQ_KSUB), 0, s, w.qrows, d.row_bytes, d.dtype, nq, m,
+                       pq->dsub, metric, pq->cb, w.lut);
     PQ_TRY(hipGetLastError());
-    hipLaunchKernelGGL(pq_scan_kernel, dim3(nq), dim3(PQ_THREADS), lut_bytes, s, w.lut, m, probes, nprobe, d.list_off, d.ids, pq->codes,
+    hipLaunchKernelGGL(scans[variant], dim3(nq), dim3(PQ_THREADS), lut_bytes, s, w.lut, m, probes, nprobe, d.list_off, d.ids, pq->codes,
                        k, metric, k_adc, w.qrows, (const uint8_t *)d.vecs, d.inv, (const uint8_t *)pq->refine, d.row_bytes, d.dtype, ids_out, dist_out, n_out);
     PQ_TRY(hipGetLastError());
     return TRI_OK;
