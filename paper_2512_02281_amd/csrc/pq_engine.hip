@@ -317,52 +317,137 @@ __device__ __forceinline__ bool pq_first_round_keeps(PqCollector &c, uint32_t k,
 // (3) the nprobe best lists of each query: best first, ties to the smaller list number.  (Small workgroups: the first
 // settle, which gives the bound that turns most later offers away, then sorts 256 composites instead of 1024, and
 // several workgroups share a compute unit.)
-constexpr uint32_t PQ_PROBE_THREADS = 256, PQ_PROBE_R = 4;
+constexpr uint32_t PQ_PROBE_THREADS = 256, PQ_PROBE_R = 8;
+// `todo` (may be null): one word per query, the kernel leaves the queries alone whose word is zero.
 __global__ __launch_bounds__(PQ_PROBE_THREADS) void pq_probe_kernel(const float *__restrict__ scores, uint32_t ldc, uint32_t nlist,
-                                                              uint32_t nprobe, uint32_t metric, uint32_t *__restrict__ probes)
+                                                              uint32_t nprobe, uint32_t metric, uint32_t *__restrict__ probes,
+                                                              const uint32_t *__restrict__ todo)
 {
     __shared__ PqCollector col;
+    if (todo && !todo[blockIdx.x]) return;
     const float *row = scores + (size_t)blockIdx.x * ldc;
     const uint32_t kind = metric == 1u ? 1u : 0u;
     pq_collect_init(col);
+    // after the first round, PQ_PROBE_R scores per thread and round (one barrier for all of them), loaded one round ahead
+    auto load = [&](uint32_t i0, float (&v)[PQ_PROBE_R]) {
+#pragma unroll
+        for (uint32_t r = 0; r < PQ_PROBE_R; ++r) {
+            const uint32_t i = i0 + r * PQ_PROBE_THREADS + threadIdx.x;
+            v[r] = i < nlist ? row[i] : 0.f;
+        }
+    };
+    float v[PQ_PROBE_R], nv[PQ_PROBE_R];
+    load(PQ_PROBE_THREADS, v);
     {   // the first 256 scores: they give the bound
         const bool valid = threadIdx.x < nlist;
         const uint64_t comp = valid ? ((uint64_t)tri_score_key(row[threadIdx.x], kind) << 32) | threadIdx.x : ~0ull;
         pq_collect_offer(col, pq_first_round_keeps<PQ_PROBE_THREADS>(col, nprobe, valid, comp), comp);
         pq_collect_close<PQ_PROBE_THREADS>(col, nprobe, PQ_PROBE_R * PQ_PROBE_THREADS);
     }
-    // then PQ_PROBE_R scores per thread and round (their loads in flight together, one barrier for all of them)
     for (uint32_t i0 = PQ_PROBE_THREADS; i0 < nlist; i0 += PQ_PROBE_R * PQ_PROBE_THREADS) {
-        float v[PQ_PROBE_R];
-#pragma unroll
-        for (uint32_t r = 0; r < PQ_PROBE_R; ++r) {
-            const uint32_t i = i0 + r * PQ_PROBE_THREADS + threadIdx.x;
-            v[r] = i < nlist ? row[i] : 0.f;
-        }
+        load(i0 + PQ_PROBE_R * PQ_PROBE_THREADS, nv);
 #pragma unroll
         for (uint32_t r = 0; r < PQ_PROBE_R; ++r) {
             const uint32_t i = i0 + r * PQ_PROBE_THREADS + threadIdx.x;
             pq_collect_offer(col, i < nlist, ((uint64_t)tri_score_key(v[r], kind) << 32) | i);
         }
         pq_collect_close<PQ_PROBE_THREADS>(col, nprobe, PQ_PROBE_R * PQ_PROBE_THREADS);
+#pragma unroll
+        for (uint32_t r = 0; r < PQ_PROBE_R; ++r) v[r] = nv[r];
     }
     pq_collect_settle<PQ_PROBE_THREADS>(col, nprobe);
     for (uint32_t i = threadIdx.x; i < nprobe; i += PQ_PROBE_THREADS)
         probes[(size_t)blockIdx.x * nprobe + i] = i < col.have ? (uint32_t)(col.buf[i] & 0xFFFFFFFFu) : 0xFFFFFFFFu;
 }
 
+// (3a) the same selection for rows of at most PQ_PW_NLIST scores and at most PQ_PW_NPROBE probes, one wavefront per
+// row with no barrier at all: the row sits in registers (64 keys per lane, read as 16 loads of 16 bytes); the
+// nprobe-th smallest of the 1024 minima of the four keys of a load and lane is found by bisection on its 32 bits with
+// ballots -- at least nprobe keys lie at or below it, so the nprobe best do; the keys at or below it (nprobe or a
+// few more) are compacted into LDS as composites by a prefix count across the lanes, ranked by counting and written
+// in rank order.  A row this does not settle (fewer than nprobe non-empty minima, or more than PQ_PW_CAP candidates:
+// masses of equal scores) gets its word of `todo` set and is left to pq_probe_kernel.
+constexpr uint32_t PQ_PW_NLIST = 4096, PQ_PW_NPROBE = 128, PQ_PW_CAP = 256, PQ_PW_ROWS = 4;
+__global__ __launch_bounds__(64 * PQ_PW_ROWS) void pq_probe_wave_kernel(const float *__restrict__ scores, uint32_t ldc, uint32_t nlist,
+                                                                        uint32_t nprobe, uint32_t metric, uint32_t nq,
+                                                                        uint32_t *__restrict__ probes, uint32_t *__restrict__ todo)
+{
+    __shared__ uint64_t cand[PQ_PW_ROWS][PQ_PW_CAP];
+    const uint32_t lane = threadIdx.x & 63, wave = (uint32_t)__builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
+    const uint32_t r = blockIdx.x * PQ_PW_ROWS + wave;
+    if (r >= nq) return;
+    const float *row = scores + (size_t)r * ldc;
+    const uint32_t kind = metric == 1u ? 1u : 0u;
+    // load j of lane l: scores 256 j + 4 l .. + 3 (rows are ldc >= nlist scores long, ldc a multiple of 4)
+    uint32_t key[16][4], mn[16];
+    float4 v[16];
+#pragma unroll
+    for (uint32_t j = 0; j < 16; ++j) {
+        const uint32_t e0 = j * 256 + lane * 4;
+        v[j] = e0 < ldc ? *(const float4 *)(row + e0) : float4{0.f, 0.f, 0.f, 0.f};
+    }
+#pragma unroll
+    for (uint32_t j = 0; j < 16; ++j) {
+        const uint32_t e0 = j * 256 + lane * 4;
+        const float x[4] = {v[j].x, v[j].y, v[j].z, v[j].w};
+#pragma unroll
+        for (uint32_t c = 0; c < 4; ++c) key[j][c] = e0 + c < nlist ? tri_score_key(x[c], kind) : 0xFFFFFFFFu;
+        const uint32_t a = key[j][0] < key[j][1] ? key[j][0] : key[j][1], b = key[j][2] < key[j][3] ? key[j][2] : key[j][3];
+        mn[j] = a < b ? a : b;
+    }
+    uint32_t T = 0;
+    for (int b = 31; b >= 0; --b) {
+        const uint32_t trial = T | ((1u << b) - 1u);                  // (bit b clear, every lower bit set)
+        uint32_t cnt = 0;
+#pragma unroll
+        for (uint32_t j = 0; j < 16; ++j) cnt += (uint32_t)__popcll(__ballot(mn[j] <= trial));
+        if (cnt < nprobe) T |= 1u << b;
+    }
+    uint32_t mine = 0;
+#pragma unroll
+    for (uint32_t j = 0; j < 16; ++j)
+#pragma unroll
+        for (uint32_t c = 0; c < 4; ++c) mine += key[j][c] <= T ? 1u : 0u;
+    uint32_t incl = mine;
+#pragma unroll
+    for (int dd = 1; dd < 64; dd <<= 1) {
+        const uint32_t o = (uint32_t)__shfl_up((int)incl, dd, 64);
+        if ((int)lane >= dd) incl += o;
+    }
+    const uint32_t total = (uint32_t)__builtin_amdgcn_readlane((int)incl, 63);
+    const bool settled = T != 0xFFFFFFFFu && total <= PQ_PW_CAP;      // (uniform)
+    if (lane == 0) todo[r] = settled ? 0u : 1u;
+    if (!settled) return;
+    uint64_t *a = cand[wave];
+    uint32_t pos = incl - mine;
+#pragma unroll
+    for (uint32_t j = 0; j < 16; ++j)
+#pragma unroll
+        for (uint32_t c = 0; c < 4; ++c)
+            if (key[j][c] <= T) a[pos++] = ((uint64_t)key[j][c] << 32) | (j * 256 + lane * 4 + c);
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    for (uint32_t i = lane; i < total; i += 64) {
+        const uint64_t x = a[i];
+        uint32_t rank = 0;
+        for (uint32_t o = 0; o < total; ++o) rank += a[o] < x ? 1u : 0u;
+        if (rank < nprobe) probes[(size_t)r * nprobe + rank] = (uint32_t)(x & 0xFFFFFFFFu);
+    }
+}
+
 // (4) tables: lut[q][mm][c] = sum over the sub-space of (q - entry)^2, or of -q * entry, in coordinate order.  A
 // workgroup makes the tables of PQ_LUT_Q queries for PQ_LUT_M sub-spaces (grid: query groups x m / PQ_LUT_M; m is a
-// multiple of 4): a codebook word read from the cache serves all its queries, a thread's codebook loads of its
-// PQ_LUT_M entries are all in flight together, and the kernel is left with writing the tables.
+// multiple of 4), one wavefront per sub-space, four entries per lane: a codebook word read from the cache serves all
+// the queries, a query value read from LDS four entries, and the kernel is left with writing the tables.
 constexpr uint32_t PQ_LUT_Q = 16, PQ_LUT_M = 4;
-__global__ __launch_bounds__(TRI_PQ_KSUB) void pq_lut_kernel(const uint8_t *__restrict__ qrows, uint32_t row_bytes, uint32_t dtype,
-                                                             uint32_t nq, uint32_t m, uint32_t dsub, uint32_t metric,
-                                                             const float *__restrict__ cb, float *__restrict__ lut)
+__global__ __launch_bounds__(64 * PQ_LUT_M) void pq_lut_kernel(const uint8_t *__restrict__ qrows, uint32_t row_bytes, uint32_t dtype,
+                                                               uint32_t nq, uint32_t m, uint32_t dsub, uint32_t metric,
+                                                               const float *__restrict__ cb, float *__restrict__ lut)
 {
     __shared__ __attribute__((aligned(16))) float qv[PQ_LUT_Q][PQ_LUT_M * TRI_PQ_DSUB_MAX];
-    const uint32_t q0 = blockIdx.x * PQ_LUT_Q, m0 = blockIdx.y * PQ_LUT_M, c = threadIdx.x, span = PQ_LUT_M * dsub;
-    for (uint32_t i = threadIdx.x; i < PQ_LUT_Q * span; i += TRI_PQ_KSUB) {
+    const uint32_t q0 = blockIdx.x * PQ_LUT_Q, m0 = blockIdx.y * PQ_LUT_M, span = PQ_LUT_M * dsub;
+    for (uint32_t i = threadIdx.x; i < PQ_LUT_Q * span; i += 64 * PQ_LUT_M) {
         const uint32_t j = i / span, e = i % span;
         const uint8_t *row = qrows + (size_t)(q0 + j < nq ? q0 + j : q0) * row_bytes;
         qv[j][e] = dtype == 1u ? (float)((const _Float16 *)row)[m0 * dsub + e] : ((const float *)row)[m0 * dsub + e];
@@ -372,35 +457,46 @@ __global__ __launch_bounds__(TRI_PQ_KSUB) void pq_lut_kernel(const uint8_t *__re
         const float d = x - y;
         return metric == 0u ? __builtin_fmaf(d, d, a) : __builtin_fmaf(-x, y, a);
     };
+    const uint32_t u = threadIdx.x >> 6, lane = threadIdx.x & 63, mm = m0 + u;      // entries lane, lane + 64, + 128, + 192
+    float acc[PQ_LUT_Q][4];
 #pragma unroll
-    for (uint32_t u = 0; u < PQ_LUT_M; ++u) {
-        const uint32_t mm = m0 + u;
-        float acc[PQ_LUT_Q];
+    for (uint32_t j = 0; j < PQ_LUT_Q; ++j)
 #pragma unroll
-        for (uint32_t j = 0; j < PQ_LUT_Q; ++j) acc[j] = 0.f;
-        if (dsub % 4 == 0) {
-            // (the query values are the same for all lanes and come four to a read)
-            for (uint32_t e = 0; e < dsub; e += 4) {
-                float y[4];
+        for (uint32_t i = 0; i < 4; ++i) acc[j][i] = 0.f;
+    if (dsub % 4 == 0) {
+        for (uint32_t e = 0; e < dsub; e += 4) {
+            float y[4][4];
 #pragma unroll
-                for (uint32_t i = 0; i < 4; ++i) y[i] = cb[pq_cb_at(mm, c, e + i, dsub)];
+            for (uint32_t i = 0; i < 4; ++i)
 #pragma unroll
-                for (uint32_t j = 0; j < PQ_LUT_Q; ++j) {
-                    const float4 x = *(const float4 *)&qv[j][u * dsub + e];
-                    acc[j] = term(x.w, y[3], term(x.z, y[2], term(x.y, y[1], term(x.x, y[0], acc[j]))));
-                }
-            }
-        } else {
-            for (uint32_t e = 0; e < dsub; ++e) {
-                const float y = cb[pq_cb_at(mm, c, e, dsub)];
+                for (uint32_t f = 0; f < 4; ++f) y[i][f] = cb[pq_cb_at(mm, lane + 64 * i, e + f, dsub)];
 #pragma unroll
-                for (uint32_t j = 0; j < PQ_LUT_Q; ++j) acc[j] = term(qv[j][u * dsub + e], y, acc[j]);
+            for (uint32_t j = 0; j < PQ_LUT_Q; ++j) {
+                const float4 x = *(const float4 *)&qv[j][u * dsub + e];
+#pragma unroll
+                for (uint32_t i = 0; i < 4; ++i)
+                    acc[j][i] = term(x.w, y[i][3], term(x.z, y[i][2], term(x.y, y[i][1], term(x.x, y[i][0], acc[j][i]))));
             }
         }
+    } else {
+        for (uint32_t e = 0; e < dsub; ++e) {
+            float y[4];
 #pragma unroll
-        for (uint32_t j = 0; j < PQ_LUT_Q; ++j)
-            if (q0 + j < nq) lut[((size_t)(q0 + j) * m + mm) * TRI_PQ_KSUB + c] = acc[j];
+            for (uint32_t i = 0; i < 4; ++i) y[i] = cb[pq_cb_at(mm, lane + 64 * i, e, dsub)];
+#pragma unroll
+            for (uint32_t j = 0; j < PQ_LUT_Q; ++j) {
+                const float x = qv[j][u * dsub + e];
+#pragma unroll
+                for (uint32_t i = 0; i < 4; ++i) acc[j][i] = term(x, y[i], acc[j][i]);
+            }
+        }
     }
+#pragma unroll
+    for (uint32_t j = 0; j < PQ_LUT_Q; ++j)
+        if (q0 + j < nq) {
+#pragma unroll
+            for (uint32_t i = 0; i < 4; ++i) lut[((size_t)(q0 + j) * m + mm) * TRI_PQ_KSUB + lane + 64 * i] = acc[j][i];
+        }
 }
 
 // (5) one workgroup per query.  G: the 16-byte groups of a code when m is a multiple of 16 (the look-ups of a code are
@@ -421,24 +517,49 @@ __global__ __launch_bounds__(PQ_THREADS) void pq_scan_kernel(const float *__rest
     __shared__ PqCollector col;
     __shared__ uint32_t first[TRI_PQ_NPROBE_MAX], start[TRI_PQ_NPROBE_MAX + 1];   // per probed list: first stored position; running sum of lengths
     const uint32_t q = blockIdx.x;
-    {
-        const float4 *src = (const float4 *)(lut + (size_t)q * m * TRI_PQ_KSUB);
-#pragma unroll 4
-        for (uint32_t t = threadIdx.x; t < m * (TRI_PQ_KSUB / 4); t += PQ_THREADS) ((float4 *)lut_lds)[t] = src[t];
-    }
-    if (threadIdx.x < 64) {
-        // (the first wavefront: lane l takes probes 4 l .. 4 l + 3, the running sums come from a scan across the lanes)
-        constexpr uint32_t PER = TRI_PQ_NPROBE_MAX / 64;
-        uint32_t len[PER], mine = 0;
+    // A query's tables on their way from memory into LDS: 16 bytes per thread and turn, held in registers between.
+    constexpr uint32_t LUT_TURNS = G ? G : PQ_GROUPS_MAX;
+    const uint32_t lut16 = m * (TRI_PQ_KSUB / 4);
+    typedef uint32_t pq_u32x4 __attribute__((ext_vector_type(4)));
+    pq_u32x4 lreg[LUT_TURNS];
+    auto lut_load = [&](uint32_t qn) {
+        const pq_u32x4 *src = (const pq_u32x4 *)(lut + (size_t)qn * m * TRI_PQ_KSUB);
+#pragma unroll
+        for (uint32_t i = 0; i < LUT_TURNS; ++i) {
+            const uint32_t t = threadIdx.x + i * PQ_THREADS;
+            if (G || t < lut16) lreg[i] = src[t];
+        }
+    };
+    auto lut_store = [&]() {
+#pragma unroll
+        for (uint32_t i = 0; i < LUT_TURNS; ++i) {
+            const uint32_t t = threadIdx.x + i * PQ_THREADS;
+            if (G || t < lut16) ((pq_u32x4 *)lut_lds)[t] = lreg[i];
+        }
+    };
+    // A query's list table, made by the first wavefront in three steps that can lie apart (each step's loads are on
+    // their way until the next one needs them): lane l takes probes 4 l .. 4 l + 3, the running sums come from a scan
+    // across the lanes.
+    constexpr uint32_t PER = TRI_PQ_NPROBE_MAX / 64;
+    uint32_t pl[PER], plo[PER], phi[PER];
+    auto lists_probes = [&](uint32_t qn) {
 #pragma unroll
         for (uint32_t j = 0; j < PER; ++j) {
             const uint32_t p = threadIdx.x * PER + j;
-            const uint32_t l = p < nprobe ? probes[(size_t)q * nprobe + p] : 0xFFFFFFFFu;
-            const uint32_t lo = l == 0xFFFFFFFFu ? 0u : list_off[l], hi = l == 0xFFFFFFFFu ? 0u : list_off[l + 1];
-            if (p < nprobe) first[p] = lo;
-            len[j] = hi - lo;
-            mine += len[j];
+            pl[j] = p < nprobe ? probes[(size_t)qn * nprobe + p] : 0xFFFFFFFFu;
         }
+    };
+    auto lists_offsets = [&]() {
+#pragma unroll
+        for (uint32_t j = 0; j < PER; ++j) {
+            plo[j] = pl[j] == 0xFFFFFFFFu ? 0u : list_off[pl[j]];
+            phi[j] = pl[j] == 0xFFFFFFFFu ? 0u : list_off[pl[j] + 1];
+        }
+    };
+    auto lists_table = [&]() {
+        uint32_t mine = 0;
+#pragma unroll
+        for (uint32_t j = 0; j < PER; ++j) mine += phi[j] - plo[j];
         uint32_t incl = mine;
 #pragma unroll
         for (int dd = 1; dd < 64; dd <<= 1) {
@@ -449,11 +570,20 @@ __global__ __launch_bounds__(PQ_THREADS) void pq_scan_kernel(const float *__rest
 #pragma unroll
         for (uint32_t j = 0; j < PER; ++j) {
             const uint32_t p = threadIdx.x * PER + j;
-            if (p < nprobe) start[p] = run;
-            run += len[j];
+            if (p < nprobe) {
+                first[p] = plo[j];
+                start[p] = run;
+            }
+            run += phi[j] - plo[j];
         }
         if (threadIdx.x == 63) start[nprobe] = run;             // (the total: probes past nprobe count nothing)
-    }
+    };
+    // (in this order the list table's two rounds of loads and the tables' loads are in flight together)
+    if (threadIdx.x < 64) lists_probes(q);
+    lut_load(q);
+    if (threadIdx.x < 64) lists_offsets();
+    lut_store();
+    if (threadIdx.x < 64) lists_table();
     pq_collect_init(col);
     // the vectors of all probed lists as ONE sequence (short lists would otherwise leave most of a round's threads
     // idle): thread t of a round takes element r0 + t and finds its list by bisection in the running sums
@@ -731,6 +861,7 @@ struct PqWs {
     float *scores;
     uint32_t *probes;
     float *lut;
+    uint32_t *todo;             // per query: its probes are still to be selected by the workgroup kernel
     size_t total;
 };
 
@@ -745,6 +876,7 @@ PqWs pq_carve(const tri_pq *pq, uint32_t nq, uint8_t *base)
     w.scores = (float *)take((size_t)nq * ldc * 4);
     w.probes = (uint32_t *)take((size_t)nq * TRI_PQ_NPROBE_MAX * 4);
     w.lut = (float *)take((size_t)nq * pq->p.m * TRI_PQ_KSUB * 4);
+    w.todo = (uint32_t *)take((size_t)nq * 4);
     w.total = off;
     return w;
 }
@@ -796,9 +928,16 @@ extern "C" int pq_search_batch(tri_pq *pq, const void *queries, size_t pitch_byt
     PQ_TRY(tri_launch_coarse_gemm(s, d.dtype == 1u ? 1 : 0, w.qrows, d.row_bytes, nq, d.centroids, d.cnorm, d.nlist, d.row_bytes,
                                   nullptr, 0u, metric, w.scores, ldc));
     uint32_t *probes = probes_out ? probes_out : w.probes;
-    hipLaunchKernelGGL(pq_probe_kernel, dim3(nq), dim3(PQ_PROBE_THREADS), 0, s, w.scores, ldc, d.nlist, nprobe, metric, probes);
+    const bool by_wave = d.nlist <= PQ_PW_NLIST && nprobe <= PQ_PW_NPROBE;
+    if (by_wave) {
+        hipLaunchKernelGGL(pq_probe_wave_kernel, dim3((nq + PQ_PW_ROWS - 1) / PQ_PW_ROWS), dim3(64 * PQ_PW_ROWS), 0, s, w.scores, ldc, d.nlist, nprobe,
+                           metric, nq, probes, w.todo);
+        PQ_TRY(hipGetLastError());
+    }
+    hipLaunchKernelGGL(pq_probe_kernel, dim3(nq), dim3(PQ_PROBE_THREADS), 0, s, w.scores, ldc, d.nlist, nprobe, metric, probes,
+                       by_wave ? (const uint32_t *)w.todo : (const uint32_t *)nullptr);
     PQ_TRY(hipGetLastError());
-    hipLaunchKernelGGL(pq_lut_kernel, dim3((nq + PQ_LUT_Q - 1) / PQ_LUT_Q, m / PQ_LUT_M), dim3(TRI_PQ_KSUB), 0, s, w.qrows, d.row_bytes, d.dtype, nq, m,
+    hipLaunchKernelGGL(pq_lut_kernel, dim3((nq + PQ_LUT_Q - 1) / PQ_LUT_Q, m / PQ_LUT_M), dim3(64 * PQ_LUT_M), 0, s, w.qrows, d.row_bytes, d.dtype, nq, m,
                        pq->dsub, metric, pq->cb, w.lut);
     PQ_TRY(hipGetLastError());
     hipLaunchKernelGGL(scans[variant], dim3(nq), dim3(PQ_THREADS), lut_bytes, s, w.lut, m, probes, nprobe, d.list_off, d.ids, pq->codes,

@@ -250,3 +250,39 @@ def test_reranked_search_against_the_two_stage_oracle(dtype, d, m, refine):
                 changed += int(not np.array_equal(got, oids[:on]))
             _say(f"pq reranked {dtype} d={d}: k={k} k_adc={k_adc} nprobe={nprobe} metric={metric}: {nq - changed} of {nq} queries exactly the oracle's ids")
             assert changed <= nq // 4
+
+
+def test_probe_lists_from_both_selection_kernels():
+    """The probe lists of a batch are chosen by one wavefront per query when the row of centroid scores is short
+    enough and one pass settles it, and by the workgroup selection otherwise (longer rows, nprobe above the wavefront
+    kernel's limit, rows it gives up on).  Integer-valued data, so every score is exact and the lists must be the
+    oracle's, in its order: 700 and 3000 distinct centroids (rows that end inside a load, rows of several loads), and
+    640 centroids that are 5 prototypes repeated 128 times -- every score ties 128 times, more equal keys than the
+    wavefront's pool holds once two prototypes are wanted, so those rows are handed over and must come out with the
+    tie rule (smaller centroid number first) intact."""
+    tri = harness.lib()
+    from paper_2512_02281_amd import pq as tpq
+    import torch
+    rng = np.random.default_rng(77)
+    dim, nq = 16, 48
+    protos = rng.integers(-8, 9, size=(5, dim)).astype(np.float32)
+    for name, cent in [("700 distinct", rng.integers(-8, 9, size=(700, dim)).astype(np.float32)),
+                       ("3000 distinct", rng.integers(-12, 13, size=(3000, dim)).astype(np.float32)),
+                       ("5 prototypes x 128", protos[np.arange(640) % 5])]:
+        nlist = cent.shape[0]
+        n = 8 * nlist
+        base = (cent[rng.integers(0, nlist, size=n)] + rng.integers(-1, 2, size=(n, dim))).astype(np.float32)
+        queries = (cent[rng.integers(0, nlist, size=nq)] + rng.integers(-1, 2, size=(nq, dim))).astype(np.float32)
+        with harness.default_pool(tri, slots=16, max_dim=dim, max_nlist=nlist, max_total_lists=nlist) as pool:
+            idx = pool.build_index(base, dim, nlist, tri.TRI_F32, tri.TRI_L2, 0, centroids=cent)
+            oidx = harness.oracle_index(tri, idx, base)
+            with tpq.PQ(pool, idx, 4, train_iters=1, seed=2) as pq:
+                qt = torch.from_numpy(queries).cuda()
+                for nprobe in (1, 7, 32, 64, 128, 129, 200):
+                    for metric in (0, 1):
+                        ids, dist, n_out, probes = _to_host(*pq.search(qt, 5, nprobe, metric))
+                        pq.sync()
+                        for i in range(nq):
+                            want = oracle.probe_set(oracle.coarse_scores(oidx, queries[i], metric), nprobe, metric)
+                            assert np.array_equal(probes[i], want), f"{name}: nprobe {nprobe} metric {metric} query {i}"
+        _say(f"pq probe lists, {name}: exactly the oracle's for nprobe 1..200, both metrics")
