@@ -517,8 +517,10 @@ def pq_bench(args, tri, workloads, torch):
                "sample": f"{cs} queries of the same batch, {dt:.1f} s of wall time; {same} of them returned exactly the GPU's ids"}
     lds_peak = 256 * 128 * 2.4          # GB/s: 256 compute units x 128 bytes of LDS per clock x 2.4 GHz
     achieved = lookups * 4 / (modes[0]["ms_per_batch"] * 1e-3) / 1e9          # (the table-score pass alone)
+    # what byte-indexed look-ups on random codes can reach at all: the scan's inner loop alone, measured now
+    bare = tpq.lds_gather_rate(m) * 4 / 1e9
     log(f"pq: {ms:.3f} ms per batch of {nq} = {nq / ms * 1e3:.0f} q/s, recall@{k} {recall}, {codes_scanned} codes x {m} look-ups "
-        f"-> {achieved:.0f} GB/s of LDS reads; build {build_s:.1f} s")
+        f"-> {achieved:.0f} GB/s of LDS reads (a bare loop of such look-ups: {bare:.0f} GB/s); build {build_s:.1f} s")
     print(json.dumps({
         "metric": "queries/sec at recall@k>=0.9 (1 GPU) + list-scan HBM GB/s as % of peak", "value": round(nq / ms * 1e3, 1), "unit": "queries/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms, 4), "higher_is_better": True, "scaling": "weak",
@@ -531,6 +533,9 @@ def pq_bench(args, tri, workloads, torch):
         "roofline": {"bound": "lds", "achieved": round(achieved, 1), "peak": lds_peak, "unit": "GB/s", "frac": round(achieved / lds_peak, 4),
                      "traffic": None, "kernel": "pq_scan_kernel + the batch's four other launches (whole batch time)",
                      "lookups_per_batch": lookups, "unique_code_bytes_per_batch": unique_bytes,
+                     "bare_lookup_loop": {"achieved": round(bare, 1), "unit": "GB/s", "frac_of_it": round(achieved / bare, 4),
+                                          "note": "the scan's inner loop alone (random bytes, m tables in LDS, one 1024-thread workgroup per "
+                                                  "compute unit), measured in this run: random indices collide on LDS banks"},
                      "note": "m 4-byte LDS look-ups per scanned code; peak = 256 compute units x 128 B of LDS per clock x 2.4 GHz; "
                              "the codes themselves (96 MB in all) are cache-resident"},
         "cpu_baseline": cpu, "wall_s_total": round(time.time() - t_start, 1)}), flush=True)

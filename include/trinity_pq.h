@@ -87,6 +87,14 @@ int pq_search_batch(tri_pq *pq, const void *queries /*[device]*/, size_t pitch_b
 
 int pq_sync(tri_pq *pq);
 
+/* Measurement helper: what the scan's look-ups can reach at most.  One workgroup of 1024 threads per compute unit
+ * holds m tables of TRI_PQ_KSUB fp32 entries in LDS and does nothing but the scan's inner loop -- four byte-indexed
+ * 4-byte look-ups per 32-bit word of random bytes, summed -- `rounds` times per thread over m / 4 words; the rate comes
+ * from HIP events around the launch on hip_stream.  lookups_per_s [host] out: look-ups per second of the whole GPU
+ * (random indices collide on LDS banks, so this lies well below the LDS's 128 bytes per clock).  m: multiple of 4,
+ * 4..124.  dev_sink [device]: 4 writable bytes.  Synchronous. */
+int pq_lds_gather_rate(uint32_t m, uint32_t rounds, void *dev_sink, void *hip_stream, double *lookups_per_s /*[host] out*/);
+
 #ifdef __cplusplus
 }
 #endif

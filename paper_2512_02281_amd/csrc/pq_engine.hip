@@ -703,7 +703,61 @@ __global__ __launch_bounds__(PQ_THREADS) void pq_scan_kernel(const float *__rest
     if (threadIdx.x == 0) n_out[q] = n;
 }
 
+// Measurement: the scan's inner loop alone -- byte-indexed look-ups into m tables in LDS, on random bytes.
+__global__ __launch_bounds__(PQ_THREADS) void pq_gather_rate_kernel(uint32_t m, uint32_t rounds, uint32_t *__restrict__ sink)
+{
+    extern __shared__ float lut_lds[];
+    for (uint32_t i = threadIdx.x; i < m * TRI_PQ_KSUB; i += PQ_THREADS) lut_lds[i] = (float)(i & 1023u);
+    __syncthreads();
+    uint32_t word = (blockIdx.x * PQ_THREADS + threadIdx.x) * 2654435761u + 12345u;
+    float sum = 0.f;
+    for (uint32_t r = 0; r < rounds; ++r) {
+#pragma unroll 4
+        for (uint32_t mm = 0; mm < m; mm += 4) {
+            word = word * 1664525u + 1013904223u;
+            const uint32_t x = word ^ (word >> 15);               // (the low bits of such a sequence repeat early)
+            const float *t = lut_lds + (size_t)mm * TRI_PQ_KSUB;
+            sum += t[x & 0xFFu];
+            sum += t[TRI_PQ_KSUB + ((x >> 8) & 0xFFu)];
+            sum += t[2 * TRI_PQ_KSUB + ((x >> 16) & 0xFFu)];
+            sum += t[3 * TRI_PQ_KSUB + (x >> 24)];
+        }
+    }
+    if (sum == -1.f) *sink = 1u;                                  // (never: the entries are not negative)
+}
+
 }  // namespace
+
+extern "C" int pq_lds_gather_rate(uint32_t m, uint32_t rounds, void *dev_sink, void *hip_stream, double *lookups_per_s)
+{
+    if (!dev_sink || !lookups_per_s || m == 0 || m % 4 || m > 124 || rounds == 0 || rounds > (1u << 20))
+        return tri_fail(TRI_EINVAL, "need m = 4..124, a multiple of 4, 1 <= rounds <= 2^20, a 4-byte device sink");
+    hipStream_t s = (hipStream_t)hip_stream;
+    int dev = 0, cus = 0;
+    PQ_TRY(hipGetDevice(&dev));
+    PQ_TRY(hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev));
+    const uint32_t lds = m * TRI_PQ_KSUB * 4;
+    PQ_TRY(hipFuncSetAttribute((const void *)pq_gather_rate_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+    hipEvent_t a = nullptr, b = nullptr;
+    hipError_t e = hipEventCreate(&a);
+    if (e == hipSuccess) e = hipEventCreate(&b);
+    float ms = 0.f;
+    for (int pass = 0; pass < 2 && e == hipSuccess; ++pass) {     // (the first pass warms up)
+        e = hipEventRecord(a, s);
+        if (e == hipSuccess) {
+            hipLaunchKernelGGL(pq_gather_rate_kernel, dim3((unsigned)cus), dim3(PQ_THREADS), lds, s, m, rounds, (uint32_t *)dev_sink);
+            e = hipGetLastError();
+        }
+        if (e == hipSuccess) e = hipEventRecord(b, s);
+        if (e == hipSuccess) e = hipEventSynchronize(b);
+        if (e == hipSuccess) e = hipEventElapsedTime(&ms, a, b);
+    }
+    if (a) (void)hipEventDestroy(a);
+    if (b) (void)hipEventDestroy(b);
+    if (e != hipSuccess) return tri_fail(TRI_EHIP, "look-up rate probe -> %s", hipGetErrorString(e));
+    *lookups_per_s = ms > 0.f ? (double)cus * PQ_THREADS * rounds * m / (ms * 1e-3) : 0.0;
+    return TRI_OK;
+}
 
 struct tri_pq {
     const tri_index *index = nullptr;

@@ -9,7 +9,8 @@ import numpy as np
 
 from . import _lib, _check, _np_ptr, TRI_OK   # noqa: F401  (the library is loaded by the package)
 
-PQ_EXPORTS = ["pq_build_bytes", "pq_build", "pq_destroy", "pq_export", "pq_search_bytes", "pq_search_batch", "pq_sync"]
+PQ_EXPORTS = ["pq_build_bytes", "pq_build", "pq_destroy", "pq_export", "pq_search_bytes", "pq_search_batch", "pq_sync",
+              "pq_lds_gather_rate"]
 TRI_PQ_KSUB = 256
 TRI_PQ_KMAX = 256
 TRI_PQ_NPROBE_MAX = 256
@@ -31,6 +32,7 @@ def _bind():
     _lib.pq_search_bytes.argtypes = [vp, u32, P(sz)]
     _lib.pq_search_batch.argtypes = [vp, vp, sz, u32, u32, u32, u32, u32, vp, sz, vp, vp, vp, vp]
     _lib.pq_sync.argtypes = [vp]
+    _lib.pq_lds_gather_rate.argtypes = [u32, u32, vp, vp, P(ctypes.c_double)]
     for name in PQ_EXPORTS:
         getattr(_lib, name).restype = ctypes.c_int
 
@@ -40,6 +42,17 @@ _bind()
 
 def _aligned(t, align=256):
     return (t.data_ptr() + align - 1) // align * align
+
+
+def lds_gather_rate(m: int, rounds: int = 200) -> float:
+    """Look-ups per second of a bare loop of the scan's byte-indexed LDS look-ups into m tables (current stream)."""
+    import torch
+    sink = torch.zeros(1, dtype=torch.int32, device="cuda")
+    out = ctypes.c_double(0.0)
+    torch.cuda.synchronize()
+    _check(_lib.pq_lds_gather_rate(m, rounds, ctypes.c_void_p(sink.data_ptr()), ctypes.c_void_p(torch.cuda.current_stream().cuda_stream),
+                                   ctypes.byref(out)), "pq_lds_gather_rate")
+    return float(out.value)
 
 
 class PQ:

@@ -286,3 +286,17 @@ def test_probe_lists_from_both_selection_kernels():
                             want = oracle.probe_set(oracle.coarse_scores(oidx, queries[i], metric), nprobe, metric)
                             assert np.array_equal(probes[i], want), f"{name}: nprobe {nprobe} metric {metric} query {i}"
         _say(f"pq probe lists, {name}: exactly the oracle's for nprobe 1..200, both metrics")
+
+
+def test_lookup_rate_probe():
+    """The measurement helper returns a plausible rate (between a thousandth of and the LDS's 128 bytes per clock and
+    compute unit at 4 bytes a look-up) and rejects what it documents."""
+    tri = harness.lib()
+    from paper_2512_02281_amd import pq as tpq
+    rate = tpq.lds_gather_rate(96, rounds=50)
+    assert 256 * 32 * 2.4e9 * 1e-3 < rate < 256 * 32 * 2.4e9 * 1.1
+    for bad in (0, 6, 128):
+        with pytest.raises(tri.TriError) as ei:
+            tpq.lds_gather_rate(bad)
+        assert ei.value.status == tri.TRI_EINVAL
+    _say(f"pq look-up rate probe: {rate / 1e12:.2f} T look-ups/s with 96 tables")
