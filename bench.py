@@ -521,7 +521,7 @@ def pq_bench(args, tri, workloads, torch):
     bare = tpq.lds_gather_rate(m) * 4 / 1e9
     log(f"pq: {ms:.3f} ms per batch of {nq} = {nq / ms * 1e3:.0f} q/s, recall@{k} {recall}, {codes_scanned} codes x {m} look-ups "
         f"-> {achieved:.0f} GB/s of LDS reads (a bare loop of such look-ups: {bare:.0f} GB/s); build {build_s:.1f} s")
-    print(json.dumps({
+    result = {
         "metric": "queries/sec at recall@k>=0.9 (1 GPU) + list-scan HBM GB/s as % of peak", "value": round(nq / ms * 1e3, 1), "unit": "queries/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms, 4), "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": "f32 tables over u8 codes of f16 vectors", "data": "synthetic",
@@ -538,9 +538,10 @@ def pq_bench(args, tri, workloads, torch):
                                                   "compute unit), measured in this run: random indices collide on LDS banks"},
                      "note": "m 4-byte LDS look-ups per scanned code; peak = 256 compute units x 128 B of LDS per clock x 2.4 GHz; "
                              "the codes themselves (96 MB in all) are cache-resident"},
-        "cpu_baseline": cpu, "wall_s_total": round(time.time() - t_start, 1)}), flush=True)
+        "cpu_baseline": cpu, "wall_s_total": round(time.time() - t_start, 1)}
     pq.close()
     pool.close()
+    return result
 
 
 def main():
@@ -570,6 +571,7 @@ def main():
                     help="run one plain device copy of this many MiB before timing (a kernel of known traffic, "
                          "to scale profiler byte counters)")
     args = ap.parse_args()
+    t_run_start = time.time()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU (the path does not shard in this round); run with --gpus 1",
               file=sys.stderr)
@@ -587,13 +589,15 @@ def main():
         print("bench.py: no GPU", file=sys.stderr)
         sys.exit(3)
     if args.workload == "graph":
-        return graph_bench(args, tri, torch)
+        print(json.dumps(graph_bench(args, tri, torch)), flush=True)
+        return
     if args.workload == "graph-stream":
         return graph_stream_bench(args, tri, torch)
     if args.workload == "rowclasses":
         return rowclass_bench(args, tri, torch)
     if args.workload == "pq":
-        return pq_bench(args, tri, workloads, torch)
+        print(json.dumps(pq_bench(args, tri, workloads, torch)), flush=True)
+        return
     number = int(args.workload[-1])
     if number == 3:
         print(json.dumps(stream_bench(args, tri, workloads, torch, brief=False)), flush=True)
@@ -628,6 +632,25 @@ def main():
                        "cpu_oracle_qps": r["cpu_baseline"]["value"] if r["cpu_baseline"] else None,
                        "cpu_cores": r["cpu_baseline"]["cores"] if r["cpu_baseline"] else None}
         result["configs"] = others
+        # the two other engines, as compact records too (their own workloads print the full ones); a failure there is
+        # recorded, never allowed to take the headline with it
+        engines = {}
+        for name, run in (("graph", lambda: graph_bench(args, tri, torch)), ("pq", lambda: pq_bench(args, tri, workloads, torch))):
+            try:
+                r = run()
+                log("full record of the %s engine: %s" % (name, json.dumps(r)))
+                rec = {"workload": r["config"]["workload"], "qps": r["value"], "ms_per_step": r["ms_per_step"],
+                       "recall_at_k": r["config"]["recall_at_k"], "bound": r["roofline"]["bound"],
+                       "achieved": r["roofline"]["achieved"], "unit": r["roofline"]["unit"], "frac": r["roofline"]["frac"],
+                       "cpu_oracle_qps": r["cpu_baseline"]["value"] if r["cpu_baseline"] else None}
+                if name == "pq":
+                    rec["modes"] = r["config"]["modes"]
+                    rec["frac_of_bare_lookup_loop"] = r["roofline"]["bare_lookup_loop"]["frac_of_it"]
+                engines[name] = rec
+            except Exception as e:          # noqa: BLE001 (whatever it is, the headline stands)
+                engines[name] = {"error": "%s: %s" % (type(e).__name__, e)}
+        result["engines"] = engines
+        result["wall_s_run"] = round(time.time() - t_run_start, 1)          # (the whole run: every configuration and engine)
     print(json.dumps(result), flush=True)
 
 
@@ -892,7 +915,7 @@ def graph_bench(args, tri, torch):
         "wall_s_total": round(time.time() - t_start, 1),
     }
     pool.close()
-    print(json.dumps(result), flush=True)
+    return result
 
 
 def graph_stream_bench(args, tri, torch):

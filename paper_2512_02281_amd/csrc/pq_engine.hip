@@ -31,6 +31,9 @@ namespace {
 
 constexpr uint32_t PQ_THREADS = 1024;     // a workgroup: 16 wavefronts, so that the LDS look-ups of a compute unit have enough in flight
 constexpr uint32_t PQ_GROUPS_MAX = 8;     // 16-byte groups of a code: m <= 128
+typedef _Float16 pq_half8 __attribute__((ext_vector_type(8)));
+typedef float pq_float4 __attribute__((ext_vector_type(4)));
+constexpr uint32_t PQ_RERANK_ROWS = 4;   // stored rows a half-wavefront re-scores at a time
 constexpr uint32_t PQ_BUF = 4096;         // composites the streaming selection holds in LDS (32 KB)
 
 size_t up256(size_t x) { return (x + 255) / 256 * 256; }
@@ -656,37 +659,59 @@ __global__ __launch_bounds__(PQ_THREADS) void pq_scan_kernel(const float *__rest
         // half-wavefront with a fixed reduction order -- and put in the order of those scores.
         const uint32_t have = col.have, l32 = threadIdx.x & 31;
         const uint8_t *qrow = qrows + (size_t)q * row_bytes;
-        for (uint32_t i = threadIdx.x >> 5; i < have; i += PQ_THREADS / 32) {
-            const uint32_t id = (uint32_t)(col.buf[i] & 0xFFFFFFFFu);
-            const uint8_t *x;
-            uint32_t piece_pitch;                                                  // distance between a row's 16-byte pieces
-            if (refine) {
-                x = refine + (size_t)id * row_bytes;
-                piece_pitch = 16u;
-            } else {
-                const uint32_t slot = inv[id];
-                x = vecs + (size_t)(slot >> 5) * tri_block_stride(row_bytes) + (slot & 31u) * 16u;
-                piece_pitch = TRI_PIECE_PITCH;
+        // (a half-wavefront works on PQ_RERANK_ROWS rows at a time, so that as many row loads are in flight per lane)
+        constexpr uint32_t HW = PQ_THREADS / 32;
+        const uint32_t piece_pitch = refine ? 16u : TRI_PIECE_PITCH;              // distance between a row's 16-byte pieces
+        const uint8_t *rows = refine ? refine : vecs;
+        for (uint32_t i0 = threadIdx.x >> 5; i0 < have; i0 += PQ_RERANK_ROWS * HW) {
+            uint32_t id[PQ_RERANK_ROWS];
+            size_t x[PQ_RERANK_ROWS];                                              // where the row starts in `rows`
+            float acc[PQ_RERANK_ROWS];
+#pragma unroll
+            for (uint32_t r = 0; r < PQ_RERANK_ROWS; ++r) {
+                const uint32_t i = i0 + r * HW;
+                id[r] = i < have ? (uint32_t)(col.buf[i] & 0xFFFFFFFFu) : 0u;
+                acc[r] = 0.f;
             }
-            float acc = 0.f;
-            for (uint32_t o = l32 * 16; o < row_bytes; o += 32 * 16) {
-                const uint4 xv = *(const uint4 *)(x + (size_t)(o / 16) * piece_pitch), qv = *(const uint4 *)(qrow + o);
-                if (dtype == 1u) {
-                    const _Float16 *xe = (const _Float16 *)&xv, *qe = (const _Float16 *)&qv;
 #pragma unroll
-                    for (int j = 0; j < 8; ++j) {
-                        const float a = (float)xe[j], b = (float)qe[j];
-                        acc = metric == 0u ? __builtin_fmaf(a - b, a - b, acc) : __builtin_fmaf(-a, b, acc);
-                    }
+            for (uint32_t r = 0; r < PQ_RERANK_ROWS; ++r) {
+                if (refine) {
+                    x[r] = (size_t)id[r] * row_bytes;
                 } else {
-                    const float *xe = (const float *)&xv, *qe = (const float *)&qv;
+                    const uint32_t slot = i0 + r * HW < have ? inv[id[r]] : 0u;
+                    x[r] = (size_t)(slot >> 5) * tri_block_stride(row_bytes) + (slot & 31u) * 16u;
+                }
+            }
+            for (uint32_t o = l32 * 16; o < row_bytes; o += 32 * 16) {
+                const uint4 qv = *(const uint4 *)(qrow + o);
+                uint4 xv[PQ_RERANK_ROWS];
 #pragma unroll
-                    for (int j = 0; j < 4; ++j) acc = metric == 0u ? __builtin_fmaf(xe[j] - qe[j], xe[j] - qe[j], acc) : __builtin_fmaf(-xe[j], qe[j], acc);
+                for (uint32_t r = 0; r < PQ_RERANK_ROWS; ++r)
+                    xv[r] = i0 + r * HW < have ? *(const uint4 *)(rows + x[r] + (size_t)(o / 16) * piece_pitch) : uint4{0u, 0u, 0u, 0u};
+#pragma unroll
+                for (uint32_t r = 0; r < PQ_RERANK_ROWS; ++r) {
+                    if (dtype == 1u) {
+                        const pq_half8 xe = __builtin_bit_cast(pq_half8, xv[r]), qe = __builtin_bit_cast(pq_half8, qv);
+#pragma unroll
+                        for (int j = 0; j < 8; ++j) {
+                            const float a = (float)xe[j], b = (float)qe[j];
+                            acc[r] = metric == 0u ? __builtin_fmaf(a - b, a - b, acc[r]) : __builtin_fmaf(-a, b, acc[r]);
+                        }
+                    } else {
+                        const pq_float4 xe = __builtin_bit_cast(pq_float4, xv[r]), qe = __builtin_bit_cast(pq_float4, qv);
+#pragma unroll
+                        for (int j = 0; j < 4; ++j)
+                            acc[r] = metric == 0u ? __builtin_fmaf(xe[j] - qe[j], xe[j] - qe[j], acc[r]) : __builtin_fmaf(-xe[j], qe[j], acc[r]);
+                    }
                 }
             }
 #pragma unroll
-            for (int dd = 16; dd > 0; dd >>= 1) acc += __shfl_xor(acc, dd, 32);
-            if (l32 == 0) col.buf[i] = ((uint64_t)tri_score_key(acc, 0u) << 32) | id;
+            for (uint32_t r = 0; r < PQ_RERANK_ROWS; ++r) {
+                float t = acc[r];
+#pragma unroll
+                for (int dd = 16; dd > 0; dd >>= 1) t += __shfl_xor(t, dd, 32);
+                if (l32 == 0 && i0 + r * HW < have) col.buf[i0 + r * HW] = ((uint64_t)tri_score_key(t, 0u) << 32) | id[r];
+            }
         }
         __syncthreads();
         pq_sort(col.buf, have);
