@@ -33,6 +33,9 @@ constexpr uint32_t PQ_THREADS = 1024;     // a workgroup: 16 wavefronts, so that
 constexpr uint32_t PQ_GROUPS_MAX = 8;     // 16-byte groups of a code: m <= 128
 typedef _Float16 pq_half8 __attribute__((ext_vector_type(8)));
 typedef float pq_float4 __attribute__((ext_vector_type(4)));
+#ifndef PQ_RANK_SORT_MAX
+#define PQ_RANK_SORT_MAX 128u            // composites up to which a sort counts ranks instead of running the network
+#endif
 constexpr uint32_t PQ_RERANK_ROWS = 4;   // stored rows a half-wavefront re-scores at a time
 constexpr uint32_t PQ_BUF = 4096;         // composites the streaming selection holds in LDS (32 KB)
 
@@ -180,12 +183,35 @@ __device__ __forceinline__ uint64_t pq_cx(uint64_t x, uint32_t lane, uint32_t s,
     return take_min ? (o < x ? o : x) : (o > x ? o : x);
 }
 
-// Bitonic sort of a[0..n) ascending (n <= PQ_BUF, padded with all-ones to a power of two >= 64); all NT threads.
-// The steps whose partners lie less than 64 apart -- most of them -- are done in registers, a wavefront per chunk of
-// 64 with lane exchanges and no barrier; only the steps with farther partners go through LDS, one barrier each.
+// Sort of a[0..n) ascending (n <= PQ_BUF); all NT threads.
+// Up to NT / 4 composites (what a selection of a few hundred holds at most times): by rank counting -- four threads
+// per composite, each of which reads a quarter of all composites (the same addresses for all lanes that work on the
+// same quarter: few LDS accesses per wavefront, none waiting for another), counts those that come before its own,
+// the four counts are added across the lanes and, after a barrier, the composite is put at that position.
+// More: a bitonic network on a[] padded with all-ones to a power of two >= 64.  The steps whose partners lie less than
+// 64 apart -- most of them -- are done in registers, a wavefront per chunk of 64 with lane exchanges and no barrier;
+// only the steps with farther partners go through LDS, one barrier each.
 template <uint32_t NT = PQ_THREADS>
 __device__ void pq_sort(uint64_t *a, uint32_t n)
 {
+    if (n <= PQ_RANK_SORT_MAX && n <= NT / 4) {                           // (uniform)
+        const uint32_t i = threadIdx.x >> 2, part = threadIdx.x & 3u;
+        uint64_t x = 0;
+        uint32_t rank = 0;
+        if (i < n) {
+            x = a[i];
+            for (uint32_t o = part; o < n; o += 4) {
+                const uint64_t y = a[o];
+                rank += (y < x || (y == x && o < i)) ? 1u : 0u;           // (equal composites keep their order)
+            }
+        }
+        rank += (uint32_t)__shfl_xor((int)rank, 1, 64);
+        rank += (uint32_t)__shfl_xor((int)rank, 2, 64);
+        __syncthreads();
+        if (i < n && part == 0) a[rank] = x;
+        __syncthreads();
+        return;
+    }
     constexpr uint32_t NW = NT / 64;
     uint32_t np2 = 64;
     while (np2 < n) np2 <<= 1;
