@@ -518,7 +518,7 @@ def pq_bench(args, tri, workloads, torch):
     lds_peak = 256 * 128 * 2.4          # GB/s: 256 compute units x 128 bytes of LDS per clock x 2.4 GHz
     achieved = lookups * 4 / (modes[0]["ms_per_batch"] * 1e-3) / 1e9          # (the table-score pass alone)
     # what byte-indexed look-ups on random codes can reach at all: the scan's inner loop alone, measured now
-    bare = tpq.lds_gather_rate(m) * 4 / 1e9
+    bare = tpq.lds_gather_rate(m, rounds=5000) * 4 / 1e9          # (35 ms: its start-up no longer shows)
     log(f"pq: {ms:.3f} ms per batch of {nq} = {nq / ms * 1e3:.0f} q/s, recall@{k} {recall}, {codes_scanned} codes x {m} look-ups "
         f"-> {achieved:.0f} GB/s of LDS reads (a bare loop of such look-ups: {bare:.0f} GB/s); build {build_s:.1f} s")
     result = {
