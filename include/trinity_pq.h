@@ -47,8 +47,9 @@ typedef struct {
 } pq_params;
 
 /* Bytes pq_build needs: dev_bytes of device memory that the tri_pq keeps (codebooks, codes, with
- * refine_rows the vectors), tmp_bytes of device
- * memory it needs only during the call (training sums).  TRI_EINVAL for an m the index's dim does not allow. */
+ * refine_rows the vectors), tmp_bytes of device memory it needs only during the call (training: the partial sums of
+ * the 16 runs the sample is dealt out in, 16 codebooks' worth; they are added in a fixed order, so the same
+ * parameters train the same codebooks bit for bit).  TRI_EINVAL for an m the index's dim does not allow. */
 int pq_build_bytes(const tri_index *index /*[host]*/, const pq_params *p /*[host]*/, size_t *dev_bytes /*[host] out*/,
                    size_t *tmp_bytes /*[host] out*/);
 

@@ -115,13 +115,9 @@ __device__ __forceinline__ uint32_t pq_nearest(const float *cb_lds, const float 
     return arg;
 }
 
-// grid (rows / 256, m): one thread per (row, sub-space); the sub-space's codebook sits in LDS.
-// TRAIN: rows are the training sample (every stride-th stored vector), the sub-vector is added to its cell's sum;
-// otherwise all stored vectors, the code is written.
-template <bool TRAIN>
-__global__ __launch_bounds__(PQ_THREADS) void pq_assign_kernel(const TriIndexDev ix, uint64_t rows, uint64_t stride, uint32_t m,
+// Encoding, grid (n / 1024, m): one thread per (stored vector, sub-space); the sub-space's codebook sits in LDS.
+__global__ __launch_bounds__(PQ_THREADS) void pq_assign_kernel(const TriIndexDev ix, uint64_t rows, uint32_t m,
                                                                uint32_t dsub, const float *__restrict__ cb,
-                                                               float *__restrict__ sums, uint32_t *__restrict__ counts,
                                                                uint8_t *__restrict__ codes)
 {
     extern __shared__ float cb_lds[];
@@ -131,27 +127,79 @@ __global__ __launch_bounds__(PQ_THREADS) void pq_assign_kernel(const TriIndexDev
     __syncthreads();
     const uint64_t r = (uint64_t)blockIdx.x * PQ_THREADS + threadIdx.x;
     if (r >= rows) return;
-    const uint64_t pos = r * stride;
+    const uint64_t pos = r;
     float x[TRI_PQ_DSUB_MAX];
     const uint32_t slot = pq_slot_of(ix, pos);
     for (uint32_t e = 0; e < dsub; ++e) x[e] = pq_elem(ix, slot, mm * dsub + e);
-    const uint32_t c = pq_nearest<TRI_PQ_DSUB_MAX>(cb_lds, x, dsub);
-    if (TRAIN) {
-        float *to = sums + ((size_t)mm * TRI_PQ_KSUB + c) * dsub;
-        for (uint32_t e = 0; e < dsub; ++e) atomicAdd(&to[e], x[e]);
-        atomicAdd(&counts[mm * TRI_PQ_KSUB + c], 1u);
-    } else {
-        codes[pq_code_at(pos, mm, m)] = (uint8_t)c;
-    }
+    codes[pq_code_at(pos, mm, m)] = (uint8_t)pq_nearest<TRI_PQ_DSUB_MAX>(cb_lds, x, dsub);
 }
 
-__global__ void pq_update_kernel(uint32_t total, uint32_t dsub, const float *__restrict__ sums,
-                                 const uint32_t *__restrict__ counts, float *__restrict__ cb)
+// One Lloyd iteration's sums, grid (PQ_TRAIN_BLOCKS, m), 256 threads: the training sample (every stride-th stored
+// vector) is dealt out in PQ_TRAIN_BLOCKS runs of consecutive rows; a workgroup takes its run 256 rows at a time --
+// thread t finds the cell of row t's sub-vector and leaves both in LDS, then thread c adds the sub-vectors of cell c
+// to its own sums in row order.  No atomics: the partial sums of the runs, added in run order by pq_update_kernel,
+// make the trained codebooks the same bit for bit on every run.
+constexpr uint32_t PQ_TRAIN_BLOCKS = 16;
+__global__ __launch_bounds__(TRI_PQ_KSUB) void pq_train_kernel(const TriIndexDev ix, uint64_t rows, uint64_t stride, uint32_t m,
+                                                               uint32_t dsub, const float *__restrict__ cb,
+                                                               float *__restrict__ part_sums, uint32_t *__restrict__ part_counts)
+{
+    extern __shared__ float cb_lds[];                                  // [256][dsub] entries, then [256][dsub] sub-vectors of the rows at hand
+    __shared__ uint32_t cell_of[TRI_PQ_KSUB];
+    float *xs = cb_lds + TRI_PQ_KSUB * dsub;
+    const uint32_t mm = blockIdx.y, t = threadIdx.x;
+    for (uint32_t i = t; i < TRI_PQ_KSUB * dsub; i += TRI_PQ_KSUB)       // i = e * 256 + c in memory -> [c][e] in LDS
+        cb_lds[(i % TRI_PQ_KSUB) * dsub + i / TRI_PQ_KSUB] = cb[(size_t)mm * TRI_PQ_KSUB * dsub + i];
+    const uint64_t per = (rows + gridDim.x - 1) / gridDim.x;
+    const uint64_t r_begin = blockIdx.x * per < rows ? blockIdx.x * per : rows, r_end = r_begin + per < rows ? r_begin + per : rows;
+    float acc[TRI_PQ_DSUB_MAX];
+#pragma unroll
+    for (uint32_t e = 0; e < TRI_PQ_DSUB_MAX; ++e) acc[e] = 0.f;
+    uint32_t cnt = 0;
+    for (uint64_t base = r_begin; base < r_end; base += TRI_PQ_KSUB) {
+        __syncthreads();                                               // (the codebook is in LDS; the last turn's rows have been read)
+        const uint64_t r = base + t;
+        uint32_t c = 0xFFFFFFFFu;
+        if (r < r_end) {
+            float x[TRI_PQ_DSUB_MAX];
+            const uint32_t slot = pq_slot_of(ix, r * stride);
+            for (uint32_t e = 0; e < dsub; ++e) x[e] = pq_elem(ix, slot, mm * dsub + e);
+            c = pq_nearest<TRI_PQ_DSUB_MAX>(cb_lds, x, dsub);
+            for (uint32_t e = 0; e < dsub; ++e) xs[t * dsub + e] = x[e];
+        }
+        cell_of[t] = c;
+        __syncthreads();
+        const uint32_t here = r_end - base < TRI_PQ_KSUB ? (uint32_t)(r_end - base) : TRI_PQ_KSUB;
+        for (uint32_t j = 0; j < here; ++j) {
+            if (cell_of[j] == t) {
+#pragma unroll
+                for (uint32_t e = 0; e < TRI_PQ_DSUB_MAX; ++e)
+                    if (e < dsub) acc[e] += xs[j * dsub + e];
+                ++cnt;
+            }
+        }
+    }
+    const size_t cell = ((size_t)blockIdx.x * m + mm) * TRI_PQ_KSUB + t;
+#pragma unroll
+    for (uint32_t e = 0; e < TRI_PQ_DSUB_MAX; ++e)
+        if (e < dsub) part_sums[cell * dsub + e] = acc[e];
+    part_counts[cell] = cnt;
+}
+
+// New entries from the runs' partial sums (added in run order); a cell nothing is nearest to keeps its entry.
+__global__ void pq_update_kernel(uint32_t total, uint32_t dsub, uint32_t runs, const float *__restrict__ part_sums,
+                                 const uint32_t *__restrict__ part_counts, float *__restrict__ cb)
 {
     const uint32_t i = blockIdx.x * blockDim.x + threadIdx.x;
     if (i >= total) return;
-    const uint32_t cell = i / dsub, cnt = counts[cell];          // (sums: [sub-space][entry][coordinate])
-    if (cnt) cb[pq_cb_at(cell / TRI_PQ_KSUB, cell % TRI_PQ_KSUB, i % dsub, dsub)] = sums[i] / (float)cnt;   // (a cell nothing is nearest to keeps its entry)
+    const uint32_t cell = i / dsub;                              // (sums: [run][sub-space][entry][coordinate])
+    float sum = 0.f;
+    uint32_t cnt = 0;
+    for (uint32_t b = 0; b < runs; ++b) {
+        sum += part_sums[(size_t)b * total + i];
+        cnt += part_counts[(size_t)b * (total / dsub) + cell];
+    }
+    if (cnt) cb[pq_cb_at(cell / TRI_PQ_KSUB, cell % TRI_PQ_KSUB, i % dsub, dsub)] = sum / (float)cnt;
 }
 
 // ---------------------------------------------------------------------------------------- search
@@ -849,7 +897,7 @@ extern "C" int pq_build_bytes(const tri_index *index, const pq_params *p, size_t
     if (rc) return rc;
     *dev_bytes = up256((size_t)p->m * TRI_PQ_KSUB * dsub * 4) + up256((size_t)(v.n + 63) / 64 * 64 * pq_mpad(p->m)) +
                  (p->refine_rows ? up256((size_t)v.n * v.dev.row_bytes) : 0);
-    *tmp_bytes = up256((size_t)p->m * TRI_PQ_KSUB * dsub * 4) + up256((size_t)p->m * TRI_PQ_KSUB * 4);
+    *tmp_bytes = up256((size_t)PQ_TRAIN_BLOCKS * p->m * TRI_PQ_KSUB * dsub * 4) + up256((size_t)PQ_TRAIN_BLOCKS * p->m * TRI_PQ_KSUB * 4);
     return TRI_OK;
 }
 
@@ -892,29 +940,25 @@ extern "C" int pq_build(const tri_index *index, const pq_params *p, const float 
                 for (uint32_t e = 0; e < dsub; ++e) t[pq_cb_at(mm, c, e, dsub)] = codebooks[((size_t)mm * TRI_PQ_KSUB + c) * dsub + e];
         PQ_TRY_B(hipMemcpy(Q->cb, t.data(), cb_bytes, hipMemcpyHostToDevice));
     } else {
-        float *sums = (float *)tmp_dev;
-        uint32_t *counts = (uint32_t *)((uint8_t *)tmp_dev + up256(cb_bytes));
+        float *sums = (float *)tmp_dev;                       // [run][sub-space][entry][coordinate]
+        uint32_t *counts = (uint32_t *)((uint8_t *)tmp_dev + up256((size_t)PQ_TRAIN_BLOCKS * cb_bytes));
         uint64_t rows = p->train_rows ? p->train_rows : 65536;
         rows = std::min<uint64_t>(rows, v.n);
         const uint64_t stride = v.n / rows;
         hipLaunchKernelGGL(pq_init_kernel, dim3(TRI_PQ_KSUB), dim3(1024), 0, s, v.dev,
                            v.n, m, dsub, p->seed, Q->cb);
         PQ_TRY_B(hipGetLastError());
+        PQ_TRY_B(hipFuncSetAttribute((const void *)pq_train_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)(2 * lds)));
         for (uint32_t it = 0; it < p->train_iters; ++it) {
-            PQ_TRY_B(tri_launch_fill_u32(s, (uint32_t *)sums, 0u, cb_bytes / 4));
-            PQ_TRY_B(tri_launch_fill_u32(s, counts, 0u, (size_t)m * TRI_PQ_KSUB));
-            hipLaunchKernelGGL(pq_assign_kernel<true>, dim3((unsigned)((rows + PQ_THREADS - 1) / PQ_THREADS), m), dim3(PQ_THREADS), lds, s,
-                               v.dev, rows, stride, m, dsub, Q->cb, sums, counts,
-                               (uint8_t *)nullptr);
+            hipLaunchKernelGGL(pq_train_kernel, dim3(PQ_TRAIN_BLOCKS, m), dim3(TRI_PQ_KSUB), 2 * lds, s, v.dev, rows, stride, m, dsub, Q->cb, sums, counts);
             PQ_TRY_B(hipGetLastError());
             const uint32_t total = m * TRI_PQ_KSUB * dsub;
-            hipLaunchKernelGGL(pq_update_kernel, dim3((total + 255) / 256), dim3(256), 0, s, total, dsub, sums, counts, Q->cb);
+            hipLaunchKernelGGL(pq_update_kernel, dim3((total + 255) / 256), dim3(256), 0, s, total, dsub, PQ_TRAIN_BLOCKS, sums, counts, Q->cb);
             PQ_TRY_B(hipGetLastError());
         }
     }
-    hipLaunchKernelGGL(pq_assign_kernel<false>, dim3((unsigned)((v.n + PQ_THREADS - 1) / PQ_THREADS), m), dim3(PQ_THREADS), lds, s,
-                       v.dev, v.n, (uint64_t)1, m, dsub, Q->cb, (float *)nullptr,
-                       (uint32_t *)nullptr, Q->codes);
+    hipLaunchKernelGGL(pq_assign_kernel, dim3((unsigned)((v.n + PQ_THREADS - 1) / PQ_THREADS), m), dim3(PQ_THREADS), lds, s, v.dev, v.n, m, dsub,
+                       Q->cb, Q->codes);
     PQ_TRY_B(hipGetLastError());
     if (Q->refine) {
         const uint64_t pieces = (uint64_t)v.n * (v.dev.row_bytes / 16);

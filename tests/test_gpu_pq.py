@@ -300,3 +300,20 @@ def test_lookup_rate_probe():
             tpq.lds_gather_rate(bad)
         assert ei.value.status == tri.TRI_EINVAL
     _say(f"pq look-up rate probe: {rate / 1e12:.2f} T look-ups/s with 96 tables")
+
+
+def test_training_is_reproducible():
+    """Training keeps no sum in an order that depends on timing: two builds with the same parameters give the same
+    codebooks and codes bit for bit (a sample that does not fill the last of the runs the rows are dealt out in)."""
+    tri = harness.lib()
+    from paper_2512_02281_amd import pq as tpq
+    n, d, nlist, m = 9000, 64, 12, 16
+    rng, base, pool, idx, oidx, torch = _setup(tri, "f32", n, d, nlist, seed=31)
+    with pool:
+        got = []
+        for _ in range(2):
+            with tpq.PQ(pool, idx, m, train_iters=5, train_rows=4100, seed=9) as pq:
+                got.append(pq.export(n, d))
+        assert np.array_equal(got[0][0].view(np.uint32), got[1][0].view(np.uint32))
+        assert np.array_equal(got[0][1], got[1][1])
+        assert np.all(np.isfinite(got[0][0]))
